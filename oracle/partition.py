@@ -1,0 +1,281 @@
+"""Oracle for the partition structure and a naive partition-wise evaluator.
+
+TEST INFRASTRUCTURE ONLY (see ``oracle/__init__.py``).
+
+What the paper fixes and this file writes out:
+
+* a partition owns its destination vertices; its gathered input ``GA_p`` is the union of the
+  source vertices of all of them (Cache-(Re)Gather-Bypass section, "(Re)gather" item);
+* the cross-partition part of that union is ordered by partition id, then vertex id
+  (appendix "In-Partition Vertex Ordering for Sequential Accesses");
+* expansion ratio ``alpha`` = required vertices / target vertices (appendix "Effect of
+  Partitioning on Host<->GPU Traffic");
+* forward of a partition: gather, aggregate along ``T_p``, transform; backward: regather,
+  recompute the aggregate, produce the gradient of the gathered rows and scatter-accumulate
+  it onto the owners, weight gradients summed over partitions (overall-procedure algorithm
+  in the appendix);
+* first/second preference of a vertex and the size penalty of the label-propagation
+  partitioner (partitioning section and its appendix).
+
+The paper's partitioner is multi-threaded and randomly initialised, so it defines no unique
+assignment.  The two deterministic rules below are this build's reading; they are written so
+that an independent implementation can reproduce them bit for bit.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+MASK64 = (1 << 64) - 1
+
+
+# ----------------------------------------------------------------------------------------
+# assignment rules
+# ----------------------------------------------------------------------------------------
+def splitmix64(x: int) -> int:
+    """One output of the SplitMix64 generator whose state before the step is ``x``."""
+    z = (x + 0x9E3779B97F4A7C15) & MASK64
+    z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & MASK64
+    z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & MASK64
+    return z ^ (z >> 31)
+
+
+def assign_random(n: int, k: int, seed: int) -> np.ndarray:
+    """Random-balanced rule: sort vertices by ``(key(v), v)`` with
+    ``key(v) = splitmix64(seed xor splitmix64(v))``; the vertex at rank ``r`` goes to
+    partition ``r mod k``.  Partition sizes differ by at most one."""
+    keys = [(splitmix64((seed & MASK64) ^ splitmix64(v)), v) for v in range(n)]
+    keys.sort()
+    part = np.empty(n, dtype=np.int32)
+    for r, (_, v) in enumerate(keys):
+        part[v] = r % k
+    return part
+
+
+def preferences(neigh_parts, k: int):
+    """Partitions ordered by how often they occur among a vertex's neighbours (most frequent
+    first, lower id first among equals); partitions that do not occur are left out."""
+    cnt = np.bincount(np.asarray(neigh_parts, dtype=np.int64), minlength=k)
+    order = sorted((j for j in range(k) if cnt[j] > 0), key=lambda j: (-cnt[j], j))
+    return order
+
+
+def lp_targets(rowptr, colidx, part, k: int) -> np.ndarray:
+    """Target partition of every vertex for one label-propagation round, from a frozen state.
+
+    The paper scores partition ``j`` for vertex ``v`` with
+    ``1 + #N(v,j)/#N(v,.) - |P_j| / (1.1 |V| / k)``.  Dropping the constant and multiplying
+    by ``11 |V| #N(v,.)`` gives the integer key ``11 |V| #N(v,j) - 10 k #N(v,.) |P_j|``,
+    which orders the partitions in the same way and makes ties exact.  ``N(v)`` is row ``v``
+    of the CSR without ``v`` itself.  Ties go to the current partition if it is among the
+    best, else to the lowest id.
+    """
+    n = len(rowptr) - 1
+    sizes = np.bincount(part, minlength=k).astype(np.int64)
+    target = np.array(part, dtype=np.int32, copy=True)
+    for v in range(n):
+        nb = colidx[rowptr[v]:rowptr[v + 1]]
+        nb = nb[nb != v]
+        deg = len(nb)
+        cnt = np.bincount(part[nb], minlength=k).astype(np.int64)
+        key = 11 * n * cnt - 10 * k * deg * sizes
+        best = key.max()
+        if key[part[v]] == best:
+            target[v] = part[v]
+        else:
+            target[v] = int(np.flatnonzero(key == best)[0])
+    return target
+
+
+def lp_targets_fast(rowptr, colidx, part, k: int) -> np.ndarray:
+    """Same result as :func:`lp_targets`, vectorised with a dense ``[n, k]`` count table so
+    that mid-size graphs finish in seconds."""
+    n = len(rowptr) - 1
+    sizes = np.bincount(part, minlength=k).astype(np.int64)
+    rows = np.repeat(np.arange(n, dtype=np.int64), np.diff(rowptr))
+    cols = np.asarray(colidx, dtype=np.int64)
+    keep = rows != cols
+    rows, cols = rows[keep], cols[keep]
+    cnt = np.bincount(rows * k + part[cols], minlength=n * k).reshape(n, k).astype(np.int64)
+    deg = cnt.sum(axis=1)
+    key = 11 * n * cnt - 10 * k * deg[:, None] * sizes[None, :]
+    best = key.max(axis=1)
+    first = np.argmax(key == best[:, None], axis=1)
+    cur = np.asarray(part, dtype=np.int64)
+    stay = key[np.arange(n), cur] == best
+    return np.where(stay, cur, first).astype(np.int32)
+
+
+def assign_lp(rowptr, colidx, k: int, seed: int, rounds: int = 10, fast: bool = True):
+    """Edge-cut rule: start from :func:`assign_random`; each round computes every vertex's
+    target from the frozen state, then one sweep in ascending vertex id moves ``v`` to its
+    target when that partition currently holds fewer than ``floor(1.1 |V| / k)`` vertices
+    (the paper's capacity limit with the balance factor 1.1)."""
+    n = len(rowptr) - 1
+    part = assign_random(n, k, seed) if n < 200_000 else assign_random_fast(n, k, seed)
+    cap = (11 * n) // (10 * k)
+    for _ in range(rounds):
+        tgt = (lp_targets_fast if fast else lp_targets)(rowptr, colidx, part, k)
+        sizes = np.bincount(part, minlength=k).astype(np.int64)
+        for v in np.flatnonzero(tgt != part):
+            j = int(tgt[v])
+            if sizes[j] < cap:
+                sizes[part[v]] -= 1
+                sizes[j] += 1
+                part[v] = j
+    return part
+
+
+def assign_random_fast(n: int, k: int, seed: int) -> np.ndarray:
+    """:func:`assign_random` with numpy uint64 arithmetic (wraps modulo 2**64)."""
+    def sm(x):
+        with np.errstate(over="ignore"):
+            z = x + np.uint64(0x9E3779B97F4A7C15)
+            z = (z ^ (z >> np.uint64(30))) * np.uint64(0xBF58476D1CE4E5B9)
+            z = (z ^ (z >> np.uint64(27))) * np.uint64(0x94D049BB133111EB)
+            return z ^ (z >> np.uint64(31))
+    v = np.arange(n, dtype=np.uint64)
+    key = sm(np.uint64(seed & MASK64) ^ sm(v))
+    order = np.lexsort((v, key))
+    part = np.empty(n, dtype=np.int32)
+    part[order] = (np.arange(n) % k).astype(np.int32)
+    return part
+
+
+# ----------------------------------------------------------------------------------------
+# partition structure by set arithmetic
+# ----------------------------------------------------------------------------------------
+def owned(part, p: int) -> np.ndarray:
+    return np.flatnonzero(np.asarray(part) == p).astype(np.int32)
+
+
+def boundary(rowptr, colidx, part, p: int) -> np.ndarray:
+    """Sources outside partition ``p`` that some vertex of ``p`` aggregates from, ordered by
+    (partition id, vertex id)."""
+    need = set()
+    for v in owned(part, p):
+        for u in colidx[rowptr[v]:rowptr[v + 1]]:
+            if part[u] != p:
+                need.add(int(u))
+    return np.array(sorted(need, key=lambda u: (int(part[u]), u)), dtype=np.int32)
+
+
+def required(rowptr, colidx, part, p: int, self_loops: bool) -> set:
+    """All vertices whose activations partition ``p`` reads: the union of the sources of its
+    destinations (with the implicit self-loop when the model adds one)."""
+    need = set()
+    for v in owned(part, p):
+        need.update(int(u) for u in colidx[rowptr[v]:rowptr[v + 1]])
+        if self_loops:
+            need.add(int(v))
+    return need
+
+
+def dependent_partitions(rowptr, colidx, part, p: int) -> list:
+    return sorted({int(part[u]) for u in boundary(rowptr, colidx, part, p)})
+
+
+def alpha(rowptr, colidx, part, k: int, self_loops: bool) -> float:
+    n = len(rowptr) - 1
+    return sum(len(required(rowptr, colidx, part, p, self_loops)) for p in range(k)) / n
+
+
+# ----------------------------------------------------------------------------------------
+# naive partition-wise evaluator (numpy, fp64)
+# ----------------------------------------------------------------------------------------
+def _operator_rows(model, rowptr, colidx):
+    """Per destination: (sources, weights) of the aggregation operator, from the definition."""
+    n = len(rowptr) - 1
+    rows = []
+    if model == "gcn":
+        nbr = []
+        for v in range(n):
+            s = set(int(u) for u in colidx[rowptr[v]:rowptr[v + 1]])
+            s.add(v)
+            nbr.append(sorted(s))
+        deg = np.array([len(s) for s in nbr], dtype=np.float64)
+        for v in range(n):
+            u = np.array(nbr[v], dtype=np.int64)
+            rows.append((u, 1.0 / np.sqrt(deg[u] * deg[v])))
+    else:
+        for v in range(n):
+            u = np.asarray(colidx[rowptr[v]:rowptr[v + 1]], dtype=np.int64)
+            rows.append((u, np.full(len(u), 1.0 / max(len(u), 1))))
+    return rows
+
+
+def partitionwise_epoch(model, rowptr, colidx, dims, X, weights, labels, mask, part, k):
+    """The paper's per-partition schedule, written naively.
+
+    forward, layer by layer, partition by partition: gather ``GA_p`` (own rows then boundary
+    rows), aggregate along ``T_p``, transform, write the partition's rows of ``A^l``;
+    backward, layers ``L..1``: zero the gradient of ``A^{l-1}``, then per partition regather,
+    recompute the aggregate, add the partition's share of the weight gradients, and for
+    ``l >= 2`` scatter-accumulate the gradient of the gathered rows onto their owners.
+    Returns the same dict layout as ``oracle.fullgraph.epoch``.
+    """
+    L = len(dims) - 1
+    n = len(rowptr) - 1
+    X = np.asarray(X, dtype=np.float64)
+    rows = _operator_rows(model, rowptr, colidx)
+    parts = []
+    for p in range(k):
+        own = owned(part, p).astype(np.int64)
+        # boundary taken from the operator's rows (the GCN self-loop never leaves a partition)
+        need = set()
+        for v in own:
+            need.update(int(u) for u in rows[v][0] if part[u] != p)
+        bnd = np.array(sorted(need, key=lambda u: (int(part[u]), u)), dtype=np.int64)
+        R = np.concatenate([own, bnd])
+        local = {int(u): i for i, u in enumerate(R)}
+        S = np.zeros((len(own), len(R)))
+        for i, v in enumerate(own):
+            u, w = rows[v]
+            for uu, ww in zip(u, w):
+                S[i, local[int(uu)]] += ww
+        parts.append((own, R, S))
+
+    Wn = [np.asarray(w["W"], dtype=np.float64) for w in weights]
+    Wsf = [np.asarray(w["Ws"], dtype=np.float64) if model == "sage" else None for w in weights]
+    bs = [np.asarray(w["b"], dtype=np.float64) if w.get("b") is not None else None
+          for w in weights]
+    act = []
+    for l in range(L):
+        Ain = X if l == 0 else act[l - 1]
+        out = np.zeros((n, dims[l + 1]))
+        for own, R, S in parts:
+            GA = Ain[R]                       # gather
+            Z = S @ GA                        # aggregate along T_p
+            Y = Z @ Wn[l]
+            if model == "sage":
+                Y = Y + Ain[own] @ Wsf[l]
+            if bs[l] is not None:
+                Y = Y + bs[l]
+            out[own] = np.maximum(Y, 0.0) if l < L - 1 else Y
+        act.append(out)
+
+    from . import fullgraph
+    lossv, G = fullgraph.loss(act[-1], labels, mask)
+    gW = [np.zeros_like(w) for w in Wn]
+    gWs = [np.zeros_like(w) if w is not None else None for w in Wsf]
+    gb = [np.zeros_like(b) if b is not None else None for b in bs]
+    gact = [None] * L
+    for l in range(L - 1, -1, -1):
+        Ain = X if l == 0 else act[l - 1]
+        gact[l] = G
+        Gprev = np.zeros((n, dims[l]))        # initialisation of the write-back buffer
+        for own, R, S in parts:
+            dY = G[own] * (act[l][own] > 0) if l < L - 1 else G[own]
+            GA = Ain[R]                       # regather
+            Z = S @ GA                        # recompute the intermediate
+            gW[l] += Z.T @ dY
+            if gb[l] is not None:
+                gb[l] += dY.sum(axis=0)
+            if model == "sage":
+                gWs[l] += Ain[own].T @ dY
+            if l >= 1:
+                dGA = S.T @ (dY @ Wn[l].T)    # gradient of the gathered rows
+                np.add.at(Gprev, R, dGA)      # scatter-accumulate
+                if model == "sage":
+                    Gprev[own] += dY @ Wsf[l].T
+        G = Gprev
+    return {"act": act, "loss": lossv, "gW": gW, "gWs": gWs, "gb": gb, "gact": gact}

@@ -1,0 +1,58 @@
+"""Small shared test utilities (no method arithmetic of the GPU path, none of the oracle's)."""
+import numpy as np
+
+from synth import rmat_graph
+
+
+def small_graph(n, m_draw, seed, symmetric=True, self_loops=False):
+    return rmat_graph(n, m_draw, seed, symmetric=symmetric, self_loops=self_loops)
+
+
+def ring_graph(n, r):
+    """r-regular ring lattice (r even): v is joined to v +- 1 .. v +- r/2."""
+    src, dst = [], []
+    for v in range(n):
+        for s in range(1, r // 2 + 1):
+            for u in ((v + s) % n, (v - s) % n):
+                src.append(u)
+                dst.append(v)
+    from synth import csr_from_edges
+    return csr_from_edges(n, np.array(src), np.array(dst))
+
+
+def complete_graph(n, self_loops):
+    from synth import csr_from_edges
+    s, t = np.meshgrid(np.arange(n), np.arange(n))
+    s, t = s.ravel(), t.ravel()
+    if not self_loops:
+        keep = s != t
+        s, t = s[keep], t[keep]
+    return csr_from_edges(n, s, t)
+
+
+def empty_graph(n):
+    return np.zeros(n + 1, dtype=np.int64), np.zeros(0, dtype=np.int32)
+
+
+def rel_err(got, ref):
+    """max |got - ref| / max |ref| over the tensor (the gate used for parity)."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    if ref.size == 0:
+        return 0.0
+    den = np.abs(ref).max()
+    num = np.abs(got - ref).max()
+    return float(num / den) if den > 0 else float(num)
+
+
+def random_weights(dims, seed, sage, bias=True):
+    rng = np.random.default_rng(seed)
+    out = []
+    for l in range(len(dims) - 1):
+        a = np.sqrt(6.0 / (dims[l] + dims[l + 1]))
+        out.append({
+            "W": rng.uniform(-a, a, (dims[l], dims[l + 1])),
+            "Ws": rng.uniform(-a, a, (dims[l], dims[l + 1])) if sage else None,
+            "b": 0.1 * rng.standard_normal(dims[l + 1]) if bias else None,
+        })
+    return out
