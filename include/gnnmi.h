@@ -1,0 +1,212 @@
+/*
+ * gnnmi - partition-wise full-graph GNN layer forward/backward on one MI355X (gfx950).
+ *
+ * C ABI of the hot path of storage-offloaded full-graph GNN training as the paper states
+ * it: the graph is split into k partitions; for every layer and every destination
+ * partition p the source activations the partition needs are gathered (GA_p), aggregated
+ * along the partition's 1-hop topology T_p and multiplied by the shared weights; the
+ * backward pass regathers instead of keeping a snapshot, recomputes the aggregate,
+ * produces the gradient of the gathered rows and scatter-accumulates it onto the owners,
+ * with weight gradients summed over partitions (Cache-(Re)Gather-Bypass section, gradient
+ * engine section, and the overall-procedure algorithm in the appendix).  The inputs are the
+ * ones that algorithm names: graph G in CSR, features F, number of partitions P (here k),
+ * number of layers L, weights W^1..W^L.
+ *
+ * General rules
+ *   - Every call returns a gnn_status; nothing throws or aborts across this boundary.
+ *   - All argument checks happen before the first HIP call of an entry point.
+ *   - "host" pointers are ordinary process memory, "device" pointers are HIP device memory
+ *     of the current device.  `stream` is a hipStream_t passed as void*.
+ *   - Layers are numbered 1..L as in the paper; A^0 is the feature matrix.
+ *   - Vertex order.  The caller's graph uses *original* vertex ids.  Per-vertex DEVICE
+ *     arrays (features, activations, gradients, labels, mask) are in *library order*: the
+ *     vertices of partition 0 first, then partition 1, ..., ascending original id inside a
+ *     partition, so that a partition's rows A_p^l are one contiguous block (the paper
+ *     stores activations per partition as well).  gnn_get_order() returns the mapping and
+ *     gnn_permute_rows() converts device arrays between the two orders.
+ *   - The library owns only the metadata it builds (host copies and their device mirrors).
+ *     Features, activations, gradients, weights, staging and scratch belong to the caller.
+ */
+#ifndef GNNMI_H
+#define GNNMI_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct gnn_ctx gnn_ctx;
+
+typedef enum {
+    GNN_OK = 0,
+    GNN_EINVAL = 1,       /* bad argument (null pointer, malformed CSR, size out of range) */
+    GNN_ENOMEM = 2,       /* host or device allocation failed / budget too small */
+    GNN_EHIP = 3,         /* a HIP runtime call failed; see gnn_last_error() */
+    GNN_ESTATE = 4,       /* call out of order (e.g. backward before forward) */
+    GNN_EUNSUPPORTED = 5  /* valid request this build does not implement */
+} gnn_status;
+
+typedef enum { GNN_GCN = 0, GNN_SAGE_MEAN = 1 } gnn_model;
+typedef enum { GNN_F32 = 0, GNN_BF16 = 1 } gnn_dtype; /* storage type of activations/weights */
+typedef enum { GNN_PART_USER = 0, GNN_PART_RANDOM = 1, GNN_PART_LP = 2 } gnn_part_mode;
+
+typedef struct {
+    int32_t model;            /* gnn_model */
+    int32_t dtype;            /* gnn_dtype */
+    int32_t n_layers;         /* L >= 1 */
+    const int32_t *dims;      /* host, L+1 entries d_0..d_L, each >= 1 (copied) */
+    int32_t has_bias;         /* 0 or 1 */
+    int64_t hbm_budget_bytes; /* 0 = everything resident in HBM */
+} gnn_config;
+
+/* Sizes the caller needs to allocate buffers and to account traffic. */
+typedef struct {
+    int64_t n;            /* vertices */
+    int64_t nnz;          /* entries of the aggregation operator (GCN: with one self-loop per vertex) */
+    int32_t k;            /* partitions */
+    int64_t sum_boundary; /* sum over p of |B_p|;  alpha = (n + sum_boundary) / n for GCN */
+    int64_t sum_required; /* sum over p of |own_p u B_p| actually referenced */
+    int64_t max_own;      /* largest n_p */
+    int64_t max_boundary; /* largest |B_p| */
+    int64_t max_nnz;      /* largest number of operator entries in one partition */
+} gnn_stats;
+
+/* Kernel classes of the profile returned by gnn_get_profile(). */
+typedef enum {
+    GNN_K_GATHER = 0,   /* boundary gather and regather */
+    GNN_K_SPMM = 1,     /* aggregation, forward and recompute */
+    GNN_K_GEMM_FWD = 2, /* Z W (+ X W_s) + b, activation */
+    GNN_K_LOSS = 3,
+    GNN_K_ACT_BWD = 4,  /* activation mask + bias gradient */
+    GNN_K_GEMM_DW = 5,  /* Z^T dY (+ X^T dY) */
+    GNN_K_GEMM_DZ = 6,  /* dY W^T (+ dY W_s^T) */
+    GNN_K_SPMM_T = 7,   /* transposed aggregation */
+    GNN_K_SCATTER = 8,  /* scatter-add onto owners */
+    GNN_K_OTHER = 9,    /* zero fills, reductions */
+    GNN_K_COUNT = 10
+} gnn_kernel_class;
+
+/* ---- lifetime -------------------------------------------------------------------------- */
+
+/* Creates a context for one model (Algorithm "overall procedure": L, the layer widths).
+ * cfg and cfg->dims are host memory, copied.  GNN_EINVAL on null/invalid fields,
+ * GNN_EUNSUPPORTED for a dtype/model this build lacks.  No HIP call is made. */
+gnn_status gnn_create(const gnn_config *cfg, gnn_ctx **out);
+
+/* Frees host and device metadata.  Null is allowed. */
+void gnn_destroy(gnn_ctx *ctx);
+
+/* Message of the last failing call on this context (or, for ctx == NULL, of the last failing
+ * gnn_create on this thread).  The string is owned by the library. */
+const char *gnn_last_error(const gnn_ctx *ctx);
+
+/* ---- partitions (host only; no HIP call) --------------------------------------------- */
+
+/* Splits the graph into k partitions and builds, per partition p: the owned vertex list,
+ * the boundary list B_p = cross-partition sources of p's destinations ordered by
+ * (partition id, vertex id) (appendix "In-Partition Vertex Ordering"), the local 1-hop
+ * topology T_p whose columns index into [own_p ; B_p], its transpose, and the
+ * normalisation factors (GCN: 1/sqrt(deg(u) deg(v)) on A + I with deg = row length of
+ * A + I; SAGE: 1/in-degree).
+ *   n, rowptr[n+1], colidx[rowptr[n]]: host CSR by destination (row v = sources u of edges
+ *     u -> v), columns strictly ascending inside a row; the arrays are only read.
+ *   mode: GNN_PART_USER takes user_part[n] (values in [0,k)); GNN_PART_RANDOM ranks the
+ *     vertices by (splitmix64(seed ^ splitmix64(v)), v) and deals ranks round-robin;
+ *     GNN_PART_LP runs 10 synchronous rounds of first-preference label propagation with the
+ *     paper's size penalty (balance factor 1.1) and capacity floor(1.1 n / k), starting
+ *     from GNN_PART_RANDOM (partitioning section and its appendix).
+ * Errors: GNN_EINVAL (null, n < 1, k < 1, k > n, malformed CSR, bad user_part),
+ * GNN_ENOMEM.  May be called again to repartition; a bound context becomes unbound. */
+gnn_status gnn_build_partitions(gnn_ctx *ctx, int64_t n, const int64_t *rowptr,
+                                const int32_t *colidx, int32_t k, int32_t mode, uint64_t seed,
+                                const int32_t *user_part);
+
+/* Read-back for bit-exact checks.  Returned host pointers stay valid until the next
+ * gnn_build_partitions or gnn_destroy.  All ids are original vertex ids. */
+gnn_status gnn_get_partition(const gnn_ctx *ctx, const int32_t **part /* n */, int32_t *k);
+gnn_status gnn_get_order(const gnn_ctx *ctx, const int32_t **order /* n: original id of row r */,
+                         const int64_t **part_offset /* k+1: first row of each partition */);
+gnn_status gnn_get_boundary(const gnn_ctx *ctx, int32_t p, const int32_t **idx, int64_t *count);
+gnn_status gnn_get_stats(const gnn_ctx *ctx, gnn_stats *out);
+
+/* Bytes the caller must provide as `staging` (largest |B_p| rows of the widest gathered
+ * layer) and `scratch` (per-partition intermediates: aggregate Z_p, dY_p, dZ_p, gradient of
+ * the gathered rows, split-K partial sums, reduction partials). */
+gnn_status gnn_workspace_bytes(const gnn_ctx *ctx, int64_t *staging, int64_t *scratch);
+
+/* ---- binding device buffers ------------------------------------------------------------ */
+
+/* Attaches the caller's device buffers (all in library order) and uploads the metadata to
+ * the current device on first use.
+ *   feat            [n, d_0]   A^0, dtype of the context
+ *   act[l-1]        [n, d_l]   A^l for l = 1..L (A^L = logits is always fp32)
+ *   grad_act[l-1]   [n, d_l]   dLoss/dA^l, fp32, for l = 1..L
+ *   weights[3*(l-1) + 0]  W^l   [d_{l-1}, d_l] row-major (GCN weight / SAGE neighbour weight)
+ *   weights[3*(l-1) + 1]  W_s^l same shape, SAGE only (else ignored, may be null)
+ *   weights[3*(l-1) + 2]  b^l   [d_l] fp32, when has_bias (else ignored, may be null)
+ *   grad_w          same layout as weights, always fp32
+ *   labels [n] int32 in [0, d_L);  train_mask [n] uint8
+ *   staging, scratch: at least gnn_workspace_bytes(), 256-byte aligned
+ * The pointer arrays themselves are host memory and are copied.
+ * Errors: GNN_ESTATE before gnn_build_partitions, GNN_EINVAL on a null entry,
+ * GNN_EHIP / GNN_ENOMEM if the upload fails. */
+gnn_status gnn_bind(gnn_ctx *ctx, const void *feat, void *const *act, void *const *grad_act,
+                    const void *const *weights, void *const *grad_w, const int32_t *labels,
+                    const uint8_t *train_mask, void *staging, void *scratch);
+
+/* dst[r] = src[order[r]] (to_library_order = 1) or dst[order[r]] = src[r] (= 0) for n rows
+ * of row_bytes bytes each; src and dst are device buffers and must not overlap. */
+gnn_status gnn_permute_rows(gnn_ctx *ctx, const void *src, void *dst, int64_t row_bytes,
+                            int32_t to_library_order, void *stream);
+
+/* ---- the hot path (enqueue on `stream`, do not synchronise) ---------------------------- */
+
+/* Gather / regather: staging[i, :] = A^{layer-1}[B_p[i], :], a bit copy of |B_p| rows
+ * (step "GA_p^{l-1} <- Gather(A^{l-1})" of the overall procedure; the same call serves the
+ * backward regather of the gradient engine).  GNN_EINVAL for layer outside 1..L or p outside
+ * 0..k-1, GNN_ESTATE when unbound. */
+gnn_status gnn_gather_boundary(gnn_ctx *ctx, int32_t layer, int32_t p, void *stream);
+
+/* A_p^l <- FW(W^l, GA_p^{l-1}, T_p): aggregation over the partition's topology reading own
+ * rows in place and boundary rows from staging, then the transform, bias and (l < L) ReLU,
+ * written to the partition's rows of act[l-1].  GNN_ESTATE unless staging holds
+ * (layer, p). */
+gnn_status gnn_layer_fwd(gnn_ctx *ctx, int32_t layer, int32_t p, void *stream);
+
+/* Mean softmax cross-entropy over the train mask on A^L and its gradient into
+ * grad_act[L-1] (rows outside the mask get zero).  Starts a new backward pass: weight
+ * gradients are NOT cleared here (gnn_epoch clears them; a caller stepping by hand clears
+ * grad_w itself).  The scalar loss stays on the device until gnn_read_loss(). */
+gnn_status gnn_loss(gnn_ctx *ctx, void *stream);
+/* Synchronises `stream` and returns the last loss. */
+gnn_status gnn_read_loss(gnn_ctx *ctx, void *stream, float *loss_out);
+
+/* (grad GA_p^{l-1}, grad W^l) <-(., +) BW(W^l, A_p^l, grad A_p^l, GA_p^{l-1}): activation
+ * mask, recomputed aggregate from the regathered staging, weight/bias gradients ADDED into
+ * grad_w, and for layer >= 2 the gradient of the gathered rows scatter-accumulated into
+ * grad_act[layer-2].  The first backward call of a layer since gnn_loss zeroes
+ * grad_act[layer-2] (the write-back buffer initialisation of the overall procedure).
+ * Partitions of one layer must be issued on one stream (the accumulation relies on stream
+ * order, not atomics).  GNN_ESTATE unless staging holds (layer, p), the forward pass and
+ * gnn_loss have run, and layer+1 has finished its backward. */
+gnn_status gnn_layer_bwd(gnn_ctx *ctx, int32_t layer, int32_t p, void *stream);
+
+/* One epoch: forward over all layers and partitions, loss, backward; grad_w is overwritten.
+ * Synchronises `stream` before writing *loss_out (host). */
+gnn_status gnn_epoch(gnn_ctx *ctx, void *stream, float *loss_out);
+
+/* ---- measurement ------------------------------------------------------------------------ */
+
+/* When enabled, every kernel launch of gnn_epoch is bracketed by HIP events on `stream`;
+ * after the epoch gnn_get_profile() returns, per kernel class, the summed duration in
+ * milliseconds and the launch count of the last epoch.  Adds event overhead; keep it off
+ * for wall-clock timing. */
+gnn_status gnn_set_profiling(gnn_ctx *ctx, int32_t enabled);
+gnn_status gnn_get_profile(const gnn_ctx *ctx, double *ms /* GNN_K_COUNT */,
+                           int64_t *launches /* GNN_K_COUNT */);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GNNMI_H */

@@ -1,0 +1,305 @@
+"""ctypes binding of ``include/gnnmi.h``: same entry points, argument marshalling only.
+
+``Context`` wraps a ``gnn_ctx*`` and exposes one method per C entry point with the same name
+minus the ``gnn_`` prefix.  ``Session`` is a convenience that allocates the device buffers
+with torch (torch is used for device memory and streams only) and binds them.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+GNN_GCN, GNN_SAGE_MEAN = 0, 1
+GNN_F32, GNN_BF16 = 0, 1
+GNN_PART_USER, GNN_PART_RANDOM, GNN_PART_LP = 0, 1, 2
+KERNEL_CLASSES = ("gather", "spmm", "gemm_fwd", "loss", "act_bwd", "gemm_dw", "gemm_dz",
+                  "spmm_t", "scatter", "other")
+STATUS = {0: "GNN_OK", 1: "GNN_EINVAL", 2: "GNN_ENOMEM", 3: "GNN_EHIP", 4: "GNN_ESTATE",
+          5: "GNN_EUNSUPPORTED"}
+_MODEL = {"gcn": GNN_GCN, "sage": GNN_SAGE_MEAN}
+_PART = {"user": GNN_PART_USER, "random": GNN_PART_RANDOM, "lp": GNN_PART_LP}
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libgnnmi.so")
+_lib = None
+
+
+class GnnError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__("%s: %s" % (STATUS.get(status, status), message))
+        self.status = status
+
+
+class _Config(C.Structure):
+    _fields_ = [("model", C.c_int32), ("dtype", C.c_int32), ("n_layers", C.c_int32),
+                ("dims", C.POINTER(C.c_int32)), ("has_bias", C.c_int32),
+                ("hbm_budget_bytes", C.c_int64)]
+
+
+class _Stats(C.Structure):
+    _fields_ = [("n", C.c_int64), ("nnz", C.c_int64), ("k", C.c_int32),
+                ("sum_boundary", C.c_int64), ("sum_required", C.c_int64),
+                ("max_own", C.c_int64), ("max_boundary", C.c_int64), ("max_nnz", C.c_int64)]
+
+
+def load_library():
+    """Loads ``libgnnmi.so`` from the package directory (build it with
+    ``python -m paper_2605_11517_amd.build``).  Raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            "%s not found: build the HIP library first (python -m paper_2605_11517_amd.build)"
+            % LIB_PATH)
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, i64, u64 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64
+    P = C.POINTER
+    sig = {
+        "gnn_create": [P(_Config), P(vp)],
+        "gnn_build_partitions": [vp, i64, P(i64), P(i32), i32, i32, u64, P(i32)],
+        "gnn_get_partition": [vp, P(P(i32)), P(i32)],
+        "gnn_get_order": [vp, P(P(i32)), P(P(i64))],
+        "gnn_get_boundary": [vp, i32, P(P(i32)), P(i64)],
+        "gnn_get_stats": [vp, P(_Stats)],
+        "gnn_workspace_bytes": [vp, P(i64), P(i64)],
+        "gnn_bind": [vp, vp, P(vp), P(vp), P(vp), P(vp), vp, vp, vp, vp],
+        "gnn_permute_rows": [vp, vp, vp, i64, i32, vp],
+        "gnn_gather_boundary": [vp, i32, i32, vp],
+        "gnn_layer_fwd": [vp, i32, i32, vp],
+        "gnn_loss": [vp, vp],
+        "gnn_read_loss": [vp, vp, P(C.c_float)],
+        "gnn_layer_bwd": [vp, i32, i32, vp],
+        "gnn_epoch": [vp, vp, P(C.c_float)],
+        "gnn_set_profiling": [vp, i32],
+        "gnn_get_profile": [vp, P(C.c_double), P(i64)],
+    }
+    for name, args in sig.items():
+        fn = getattr(lib, name)
+        fn.argtypes = args
+        fn.restype = C.c_int
+    lib.gnn_destroy.argtypes = [vp]
+    lib.gnn_destroy.restype = None
+    lib.gnn_last_error.argtypes = [vp]
+    lib.gnn_last_error.restype = C.c_char_p
+    _lib = lib
+    return lib
+
+
+def _np_ptr(a, t):
+    return a.ctypes.data_as(C.POINTER(t))
+
+
+class Context:
+    """Owns one ``gnn_ctx``.  Methods mirror the C entry points and raise ``GnnError``."""
+
+    def __init__(self, model, dims, dtype=GNN_F32, has_bias=True, hbm_budget_bytes=0):
+        self.lib = load_library()
+        self.model = _MODEL.get(model, model)
+        self.dims = [int(d) for d in dims]
+        self.L = len(self.dims) - 1
+        arr = (C.c_int32 * len(self.dims))(*self.dims)
+        cfg = _Config(self.model, dtype, self.L, arr, 1 if has_bias else 0, hbm_budget_bytes)
+        h = C.c_void_p()
+        st = self.lib.gnn_create(C.byref(cfg), C.byref(h))
+        if st != 0:
+            raise GnnError(st, self.lib.gnn_last_error(None).decode())
+        self.h = h
+        self._keep = []
+
+    def _check(self, st):
+        if st != 0:
+            raise GnnError(st, self.lib.gnn_last_error(self.h).decode())
+
+    def destroy(self):
+        if getattr(self, "h", None):
+            self.lib.gnn_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+    # -- partitions (host) ------------------------------------------------------------------
+    def build_partitions(self, rowptr, colidx, k, mode="random", seed=0, user_part=None):
+        rowptr = np.ascontiguousarray(rowptr, dtype=np.int64)
+        colidx = np.ascontiguousarray(colidx, dtype=np.int32)
+        n = len(rowptr) - 1
+        up = None
+        if user_part is not None:
+            up = np.ascontiguousarray(user_part, dtype=np.int32)
+        self._check(self.lib.gnn_build_partitions(
+            self.h, n, _np_ptr(rowptr, C.c_int64), _np_ptr(colidx, C.c_int32), int(k),
+            _PART.get(mode, mode), C.c_uint64(seed & (2 ** 64 - 1)),
+            _np_ptr(up, C.c_int32) if up is not None else None))
+        self.n = n
+        self.k = int(k)
+
+    def get_partition(self):
+        p = C.POINTER(C.c_int32)()
+        k = C.c_int32()
+        self._check(self.lib.gnn_get_partition(self.h, C.byref(p), C.byref(k)))
+        return np.ctypeslib.as_array(p, shape=(self.n,)).copy(), int(k.value)
+
+    def get_order(self):
+        o = C.POINTER(C.c_int32)()
+        off = C.POINTER(C.c_int64)()
+        self._check(self.lib.gnn_get_order(self.h, C.byref(o), C.byref(off)))
+        return (np.ctypeslib.as_array(o, shape=(self.n,)).copy(),
+                np.ctypeslib.as_array(off, shape=(self.k + 1,)).copy())
+
+    def get_boundary(self, p):
+        idx = C.POINTER(C.c_int32)()
+        cnt = C.c_int64()
+        self._check(self.lib.gnn_get_boundary(self.h, int(p), C.byref(idx), C.byref(cnt)))
+        if cnt.value == 0:
+            return np.zeros(0, dtype=np.int32)
+        return np.ctypeslib.as_array(idx, shape=(cnt.value,)).copy()
+
+    def get_stats(self):
+        s = _Stats()
+        self._check(self.lib.gnn_get_stats(self.h, C.byref(s)))
+        return {f: getattr(s, f) for f, _ in _Stats._fields_}
+
+    def workspace_bytes(self):
+        a, b = C.c_int64(), C.c_int64()
+        self._check(self.lib.gnn_workspace_bytes(self.h, C.byref(a), C.byref(b)))
+        return int(a.value), int(b.value)
+
+    # -- device side (pointers are raw device addresses, stream a raw hipStream_t) ------------
+    def bind(self, feat, act, grad_act, weights, grad_w, labels, train_mask, staging, scratch):
+        def arr(ptrs):
+            a = (C.c_void_p * max(1, len(ptrs)))()
+            for i, p in enumerate(ptrs):
+                a[i] = p
+            return a
+        self._check(self.lib.gnn_bind(self.h, feat, arr(act), arr(grad_act), arr(weights),
+                                      arr(grad_w), labels, train_mask, staging, scratch))
+
+    def permute_rows(self, src, dst, row_bytes, to_library_order, stream):
+        self._check(self.lib.gnn_permute_rows(self.h, src, dst, int(row_bytes),
+                                              1 if to_library_order else 0, stream))
+
+    def gather_boundary(self, layer, p, stream):
+        self._check(self.lib.gnn_gather_boundary(self.h, int(layer), int(p), stream))
+
+    def layer_fwd(self, layer, p, stream):
+        self._check(self.lib.gnn_layer_fwd(self.h, int(layer), int(p), stream))
+
+    def loss(self, stream):
+        self._check(self.lib.gnn_loss(self.h, stream))
+
+    def read_loss(self, stream):
+        v = C.c_float()
+        self._check(self.lib.gnn_read_loss(self.h, stream, C.byref(v)))
+        return float(v.value)
+
+    def layer_bwd(self, layer, p, stream):
+        self._check(self.lib.gnn_layer_bwd(self.h, int(layer), int(p), stream))
+
+    def epoch(self, stream):
+        v = C.c_float()
+        self._check(self.lib.gnn_epoch(self.h, stream, C.byref(v)))
+        return float(v.value)
+
+    def set_profiling(self, enabled):
+        self._check(self.lib.gnn_set_profiling(self.h, 1 if enabled else 0))
+
+    def get_profile(self):
+        ms = (C.c_double * len(KERNEL_CLASSES))()
+        ln = (C.c_int64 * len(KERNEL_CLASSES))()
+        self._check(self.lib.gnn_get_profile(self.h, ms, ln))
+        return {name: (float(ms[i]), int(ln[i])) for i, name in enumerate(KERNEL_CLASSES)}
+
+
+class Session:
+    """Allocates every device buffer of one model on ``cuda:0`` with torch, converts the
+    caller's original-order host arrays to library order with ``gnn_permute_rows`` and binds
+    them.  Results are read back in original vertex order."""
+
+    def __init__(self, model, dims, rowptr, colidx, k, part_mode, seed, X, weights, labels,
+                 train_mask, has_bias=True, user_part=None, device="cuda:0"):
+        import torch
+        self.torch = torch
+        if not torch.cuda.is_available():
+            raise RuntimeError("gnnmi needs a GPU: torch.cuda.is_available() is False")
+        self.dev = torch.device(device)
+        self.ctx = Context(model, dims, has_bias=has_bias)
+        self.ctx.build_partitions(rowptr, colidx, k, part_mode, seed, user_part)
+        self.model = _MODEL.get(model, model)
+        self.dims = list(dims)
+        self.L = len(dims) - 1
+        self.n = self.ctx.n
+        self.has_bias = has_bias
+        t = torch
+        stream = self.stream
+        # inputs: upload in original order, permute on the device
+        self.feat = self._to_library(t.from_numpy(np.ascontiguousarray(X, dtype=np.float32)))
+        self.labels = self._to_library(t.from_numpy(np.ascontiguousarray(labels, dtype=np.int32)))
+        self.mask = self._to_library(t.from_numpy(np.ascontiguousarray(train_mask, dtype=np.uint8)))
+        self.act = [t.zeros((self.n, dims[l + 1]), dtype=t.float32, device=self.dev)
+                    for l in range(self.L)]
+        self.gact = [t.zeros((self.n, dims[l + 1]), dtype=t.float32, device=self.dev)
+                     for l in range(self.L)]
+        self.w, self.gw = [], []
+        for l in range(self.L):
+            for key in ("W", "Ws", "b"):
+                a = weights[l].get(key)
+                use = a is not None and (key != "Ws" or self.model == GNN_SAGE_MEAN) \
+                    and (key != "b" or has_bias)
+                if use:
+                    wt = t.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(self.dev)
+                    self.w.append(wt)
+                    self.gw.append(t.zeros_like(wt))
+                else:
+                    self.w.append(None)
+                    self.gw.append(None)
+        sb, wb = self.ctx.workspace_bytes()
+        self.staging = t.empty(sb, dtype=t.uint8, device=self.dev)
+        self.scratch = t.empty(wb, dtype=t.uint8, device=self.dev)
+        ptr = lambda x: x.data_ptr() if x is not None else None
+        self.ctx.bind(ptr(self.feat), [ptr(a) for a in self.act], [ptr(g) for g in self.gact],
+                      [ptr(w) for w in self.w], [ptr(g) for g in self.gw], ptr(self.labels),
+                      ptr(self.mask), ptr(self.staging), ptr(self.scratch))
+        t.cuda.synchronize()
+        del stream
+
+    @property
+    def stream(self):
+        return self.torch.cuda.current_stream(self.dev).cuda_stream
+
+    def _to_library(self, host_tensor):
+        t = self.torch
+        src = host_tensor.to(self.dev)
+        dst = t.empty_like(src)
+        row_bytes = src.element_size() * (src.shape[1] if src.dim() == 2 else 1)
+        self.ctx.permute_rows(src.data_ptr(), dst.data_ptr(), row_bytes, True, self.stream)
+        t.cuda.synchronize()
+        return dst
+
+    def to_original(self, dev_tensor):
+        """Device tensor in library order -> numpy array in original vertex order."""
+        t = self.torch
+        dst = t.empty_like(dev_tensor)
+        row_bytes = dev_tensor.element_size() * (dev_tensor.shape[1] if dev_tensor.dim() == 2 else 1)
+        self.ctx.permute_rows(dev_tensor.data_ptr(), dst.data_ptr(), row_bytes, False, self.stream)
+        t.cuda.synchronize()
+        return dst.cpu().numpy()
+
+    def epoch(self):
+        return self.ctx.epoch(self.stream)
+
+    def results(self):
+        """Everything the oracle also returns, in original vertex order."""
+        out = {"act": [self.to_original(a) for a in self.act],
+               "gact": [self.to_original(g) for g in self.gact],
+               "gW": [], "gWs": [], "gb": []}
+        for l in range(self.L):
+            gW, gWs, gb = self.gw[3 * l:3 * l + 3]
+            out["gW"].append(gW.cpu().numpy())
+            out["gWs"].append(gWs.cpu().numpy() if gWs is not None else None)
+            out["gb"].append(gb.cpu().numpy() if gb is not None else None)
+        return out

@@ -1,0 +1,628 @@
+// C ABI of libgnnmi: context, validation, device mirrors of the partition metadata, and the
+// per-(layer, partition) schedule of the paper's overall procedure (forward: gather, FW;
+// backward: regather, BW, scatter-accumulate).
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "gnn_internal.h"
+
+using namespace gnnmi;
+
+namespace {
+
+thread_local std::string g_create_error;
+
+constexpr int64_t kAlign = 256;
+int64_t align_up(int64_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+struct DevMeta {
+    int64_t* rp = nullptr;
+    int32_t* lcol = nullptr;
+    float* ew = nullptr;
+    float* rscale = nullptr;
+    int32_t* bnd = nullptr;
+    int64_t* trp = nullptr;
+    int32_t* tcol = nullptr;
+    float* tw = nullptr;
+    int32_t* order = nullptr;
+    bool ready = false;
+};
+
+struct Workspace {  // byte offsets into `scratch`
+    int64_t z = 0, dy = 0, dz = 0, dga = 0, partial = 0, colpart = 0, losspart = 0, scalars = 0;
+    int64_t staging_bytes = 0, scratch_bytes = 0;
+};
+
+}  // namespace
+
+struct gnn_ctx {
+    int32_t model = 0, dtype = 0, L = 0, has_bias = 1;
+    int64_t hbm_budget = 0;
+    std::vector<int32_t> dims;
+    mutable std::string err;
+    bool built = false, bound = false;
+    HostMeta M;
+    DevMeta D;
+    Workspace ws;
+    // bound buffers
+    const float* feat = nullptr;
+    std::vector<float*> act, gact;
+    std::vector<const float*> w;
+    std::vector<float*> gw;
+    const int32_t* labels = nullptr;
+    const uint8_t* mask = nullptr;
+    char* staging = nullptr;
+    char* scratch = nullptr;
+    // schedule state
+    int32_t staged_layer = -1, staged_p = -1;
+    std::vector<uint8_t> fwd_done;      // L * k
+    std::vector<int32_t> bwd_done;      // per layer: partitions finished since gnn_loss
+    bool loss_done = false;
+    // profiling
+    bool prof = false;
+    std::vector<hipEvent_t> events;
+    std::vector<int> event_class;
+    size_t events_used = 0;
+    double prof_ms[GNN_K_COUNT] = {0};
+    int64_t prof_launches[GNN_K_COUNT] = {0};
+
+    gnn_status fail(gnn_status st, const std::string& msg) const
+    {
+        err = msg;
+        return st;
+    }
+    const float* layer_input(int32_t layer) const { return layer == 1 ? feat : act[(size_t)layer - 2]; }
+};
+
+namespace {
+
+void free_device(DevMeta& D)
+{
+    if (D.rp) (void)hipFree(D.rp);
+    if (D.lcol) (void)hipFree(D.lcol);
+    if (D.ew) (void)hipFree(D.ew);
+    if (D.rscale) (void)hipFree(D.rscale);
+    if (D.bnd) (void)hipFree(D.bnd);
+    if (D.trp) (void)hipFree(D.trp);
+    if (D.tcol) (void)hipFree(D.tcol);
+    if (D.tw) (void)hipFree(D.tw);
+    if (D.order) (void)hipFree(D.order);
+    D = DevMeta{};
+}
+
+template <typename T>
+hipError_t upload(T*& dst, const std::vector<T>& src)
+{
+    dst = nullptr;
+    if (src.empty()) return hipSuccess;
+    hipError_t e = hipMalloc((void**)&dst, src.size() * sizeof(T));
+    if (e != hipSuccess) return e;
+    return hipMemcpy(dst, src.data(), src.size() * sizeof(T), hipMemcpyHostToDevice);
+}
+
+gnn_status ensure_device(gnn_ctx* c)
+{
+    if (c->D.ready) return GNN_OK;
+    DevMeta& D = c->D;
+    const HostMeta& M = c->M;
+    hipError_t e = hipSuccess;
+    auto step = [&](hipError_t r) { if (e == hipSuccess) e = r; };
+    step(upload(D.rp, M.rp));
+    step(upload(D.lcol, M.lcol));
+    step(upload(D.ew, M.ew));
+    step(upload(D.rscale, M.rscale));
+    step(upload(D.bnd, M.bnd));
+    step(upload(D.trp, M.trp));
+    step(upload(D.tcol, M.tcol));
+    step(upload(D.tw, M.tw));
+    step(upload(D.order, M.order));
+    if (e != hipSuccess) {
+        free_device(D);
+        (void)hipGetLastError();
+        return c->fail(e == hipErrorOutOfMemory ? GNN_ENOMEM : GNN_EHIP,
+                       std::string("uploading partition metadata: ") + hipGetErrorString(e));
+    }
+    D.ready = true;
+    return GNN_OK;
+}
+
+void compute_workspace(gnn_ctx* c)
+{
+    const HostMeta& M = c->M;
+    const int32_t L = c->L;
+    int64_t max_np = M.stats.max_own, max_b = M.stats.max_boundary, max_r = 0;
+    for (int32_t p = 0; p < M.k; ++p)
+        max_r = std::max(max_r, M.toff[(size_t)p + 1] - M.toff[(size_t)p]);
+    int64_t din = 0, dout = 0, part = 0;
+    for (int32_t l = 0; l < L; ++l) {
+        din = std::max<int64_t>(din, c->dims[(size_t)l]);
+        dout = std::max<int64_t>(dout, c->dims[(size_t)l + 1]);
+        int sp = gemm_tn_splits(max_np, c->dims[(size_t)l], c->dims[(size_t)l + 1]);
+        part = std::max(part, (int64_t)sp * c->dims[(size_t)l] * c->dims[(size_t)l + 1]);
+    }
+    Workspace& w = c->ws;
+    w.staging_bytes = align_up(std::max<int64_t>(1, max_b * din * 4));
+    int64_t o = 0;
+    auto take = [&](int64_t floats) { int64_t at = o; o += align_up(std::max<int64_t>(1, floats) * 4); return at; };
+    w.z = take(max_np * din);
+    w.dy = take(max_np * dout);
+    w.dz = take(max_np * din);
+    w.dga = take(max_r * din);
+    w.partial = take(part);
+    w.colpart = take(act_bwd_partial_floats(max_np, (int32_t)dout));
+    w.losspart = take(loss_partial_floats(M.n));
+    w.scalars = take(64);
+    w.scratch_bytes = o;
+}
+
+// ---- profiling brackets ---------------------------------------------------------------------
+struct Timed {
+    gnn_ctx* c;
+    hipStream_t s;
+    Timed(gnn_ctx* ctx, hipStream_t st, int cls) : c(ctx), s(st)
+    {
+        if (!c->prof) return;
+        mark(cls);
+    }
+    ~Timed()
+    {
+        if (!c->prof) return;
+        mark(-1);
+    }
+    void mark(int cls)
+    {
+        if (c->events_used == c->events.size()) {
+            hipEvent_t e;
+            if (hipEventCreate(&e) != hipSuccess) return;
+            c->events.push_back(e);
+            c->event_class.push_back(0);
+        }
+        c->event_class[c->events_used] = cls;
+        (void)hipEventRecord(c->events[c->events_used], s);
+        ++c->events_used;
+    }
+};
+
+void collect_profile(gnn_ctx* c)
+{
+    for (int i = 0; i < GNN_K_COUNT; ++i) { c->prof_ms[i] = 0; c->prof_launches[i] = 0; }
+    for (size_t i = 0; i + 1 < c->events_used; i += 2) {
+        int cls = c->event_class[i];
+        float ms = 0.f;
+        if (cls >= 0 && cls < GNN_K_COUNT &&
+            hipEventElapsedTime(&ms, c->events[i], c->events[i + 1]) == hipSuccess) {
+            c->prof_ms[cls] += ms;
+            c->prof_launches[cls] += 1;
+        }
+    }
+    c->events_used = 0;
+}
+
+gnn_status check_launch(gnn_ctx* c, const char* what)
+{
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return c->fail(GNN_EHIP, std::string(what) + ": " + hipGetErrorString(e));
+    return GNN_OK;
+}
+
+gnn_status check_lp(gnn_ctx* c, int32_t layer, int32_t p)
+{
+    if (!c->bound) return c->fail(GNN_ESTATE, "buffers are not bound (call gnn_bind)");
+    if (layer < 1 || layer > c->L) return c->fail(GNN_EINVAL, "layer outside 1..L");
+    if (p < 0 || p >= c->M.k) return c->fail(GNN_EINVAL, "partition outside 0..k-1");
+    return GNN_OK;
+}
+
+// Z_p = S_p [own rows ; staging]
+void run_spmm_fwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
+{
+    const HostMeta& M = c->M;
+    const int64_t r0 = M.off[(size_t)p], np = M.off[(size_t)p + 1] - r0;
+    const int32_t din = c->dims[(size_t)layer - 1];
+    const float* in = c->layer_input(layer);
+    launch_spmm(c->D.rp + r0, c->D.lcol, c->D.ew, c->D.rscale ? c->D.rscale + r0 : nullptr,
+                in + r0 * din, np, (const float*)c->staging, (float*)(c->scratch + c->ws.z), np, din,
+                s);
+}
+
+}  // namespace
+
+// =================================================================================================
+extern "C" {
+
+gnn_status gnn_create(const gnn_config* cfg, gnn_ctx** out)
+{
+    auto bad = [&](gnn_status st, const char* m) { g_create_error = m; return st; };
+    if (!cfg || !out) return bad(GNN_EINVAL, "cfg and out must be non-null");
+    *out = nullptr;
+    if (cfg->model != GNN_GCN && cfg->model != GNN_SAGE_MEAN) return bad(GNN_EINVAL, "unknown model");
+    if (cfg->dtype != GNN_F32 && cfg->dtype != GNN_BF16) return bad(GNN_EINVAL, "unknown dtype");
+    if (cfg->n_layers < 1 || cfg->n_layers > 64) return bad(GNN_EINVAL, "n_layers must be in 1..64");
+    if (!cfg->dims) return bad(GNN_EINVAL, "dims is null");
+    for (int32_t l = 0; l <= cfg->n_layers; ++l)
+        if (cfg->dims[l] < 1 || cfg->dims[l] > (1 << 20)) return bad(GNN_EINVAL, "layer width out of range");
+    if (cfg->has_bias != 0 && cfg->has_bias != 1) return bad(GNN_EINVAL, "has_bias must be 0 or 1");
+    if (cfg->hbm_budget_bytes < 0) return bad(GNN_EINVAL, "hbm_budget_bytes must be >= 0");
+    if (cfg->dtype == GNN_BF16) return bad(GNN_EUNSUPPORTED, "bf16 storage is not implemented yet");
+    if (cfg->hbm_budget_bytes != 0)
+        return bad(GNN_EUNSUPPORTED, "streaming from pinned host memory is not implemented yet");
+    gnn_ctx* c = new (std::nothrow) gnn_ctx();
+    if (!c) return bad(GNN_ENOMEM, "out of host memory");
+    c->model = cfg->model;
+    c->dtype = cfg->dtype;
+    c->L = cfg->n_layers;
+    c->has_bias = cfg->has_bias;
+    c->hbm_budget = cfg->hbm_budget_bytes;
+    c->dims.assign(cfg->dims, cfg->dims + cfg->n_layers + 1);
+    *out = c;
+    return GNN_OK;
+}
+
+void gnn_destroy(gnn_ctx* c)
+{
+    if (!c) return;
+    if (c->D.ready) free_device(c->D);
+    for (hipEvent_t e : c->events) (void)hipEventDestroy(e);
+    delete c;
+}
+
+const char* gnn_last_error(const gnn_ctx* c) { return c ? c->err.c_str() : g_create_error.c_str(); }
+
+gnn_status gnn_build_partitions(gnn_ctx* c, int64_t n, const int64_t* rowptr, const int32_t* colidx,
+                                int32_t k, int32_t mode, uint64_t seed, const int32_t* user_part)
+{
+    if (!c) return GNN_EINVAL;
+    gnn_status st;
+    try {
+        HostMeta M;
+        std::string err;
+        st = build_host_meta(c->model, n, rowptr, colidx, k, mode, seed, user_part, M, err);
+        if (st != GNN_OK) return c->fail(st, err);
+        if (c->D.ready) free_device(c->D);
+        c->M = std::move(M);
+    } catch (const std::bad_alloc&) {
+        return c->fail(GNN_ENOMEM, "out of host memory while building partitions");
+    } catch (...) {
+        return c->fail(GNN_ENOMEM, "failed to build partitions (could not start worker threads?)");
+    }
+    c->built = true;
+    c->bound = false;
+    c->staged_layer = c->staged_p = -1;
+    c->loss_done = false;
+    c->fwd_done.assign((size_t)c->L * (size_t)k, 0);
+    c->bwd_done.assign((size_t)c->L + 2, 0);
+    compute_workspace(c);
+    return GNN_OK;
+}
+
+gnn_status gnn_get_partition(const gnn_ctx* c, const int32_t** part, int32_t* k)
+{
+    if (!c || !part || !k) return GNN_EINVAL;
+    if (!c->built) return c->fail(GNN_ESTATE, "no partitions built");
+    *part = c->M.part.data();
+    *k = c->M.k;
+    return GNN_OK;
+}
+
+gnn_status gnn_get_order(const gnn_ctx* c, const int32_t** order, const int64_t** part_offset)
+{
+    if (!c || !order || !part_offset) return GNN_EINVAL;
+    if (!c->built) return c->fail(GNN_ESTATE, "no partitions built");
+    *order = c->M.order.data();
+    *part_offset = c->M.off.data();
+    return GNN_OK;
+}
+
+gnn_status gnn_get_boundary(const gnn_ctx* c, int32_t p, const int32_t** idx, int64_t* count)
+{
+    if (!c || !idx || !count) return GNN_EINVAL;
+    if (!c->built) return c->fail(GNN_ESTATE, "no partitions built");
+    if (p < 0 || p >= c->M.k) return c->fail(GNN_EINVAL, "partition outside 0..k-1");
+    *idx = c->M.bnd_orig.data() + c->M.boff[(size_t)p];
+    *count = c->M.boff[(size_t)p + 1] - c->M.boff[(size_t)p];
+    return GNN_OK;
+}
+
+gnn_status gnn_get_stats(const gnn_ctx* c, gnn_stats* out)
+{
+    if (!c || !out) return GNN_EINVAL;
+    if (!c->built) return c->fail(GNN_ESTATE, "no partitions built");
+    *out = c->M.stats;
+    return GNN_OK;
+}
+
+gnn_status gnn_workspace_bytes(const gnn_ctx* c, int64_t* staging, int64_t* scratch)
+{
+    if (!c || !staging || !scratch) return GNN_EINVAL;
+    if (!c->built) return c->fail(GNN_ESTATE, "no partitions built");
+    *staging = c->ws.staging_bytes;
+    *scratch = c->ws.scratch_bytes;
+    return GNN_OK;
+}
+
+gnn_status gnn_bind(gnn_ctx* c, const void* feat, void* const* act, void* const* grad_act,
+                    const void* const* weights, void* const* grad_w, const int32_t* labels,
+                    const uint8_t* train_mask, void* staging, void* scratch)
+{
+    if (!c) return GNN_EINVAL;
+    if (!c->built) return c->fail(GNN_ESTATE, "gnn_bind before gnn_build_partitions");
+    if (!feat || !act || !grad_act || !weights || !grad_w || !labels || !train_mask || !staging ||
+        !scratch)
+        return c->fail(GNN_EINVAL, "null buffer passed to gnn_bind");
+    const int32_t L = c->L;
+    for (int32_t l = 0; l < L; ++l) {
+        if (!act[l] || !grad_act[l]) return c->fail(GNN_EINVAL, "null activation or gradient buffer");
+        if (!weights[3 * l] || !grad_w[3 * l]) return c->fail(GNN_EINVAL, "null weight or weight-gradient buffer");
+        if (c->model == GNN_SAGE_MEAN && (!weights[3 * l + 1] || !grad_w[3 * l + 1]))
+            return c->fail(GNN_EINVAL, "null self-weight buffer for a SAGE layer");
+        if (c->has_bias && (!weights[3 * l + 2] || !grad_w[3 * l + 2]))
+            return c->fail(GNN_EINVAL, "null bias buffer although has_bias is set");
+    }
+    if ((reinterpret_cast<uintptr_t>(staging) | reinterpret_cast<uintptr_t>(scratch) |
+         reinterpret_cast<uintptr_t>(feat)) & 15)
+        return c->fail(GNN_EINVAL, "feat, staging and scratch must be 16-byte aligned");
+    gnn_status st = ensure_device(c);
+    if (st != GNN_OK) return st;
+    c->feat = (const float*)feat;
+    c->act.assign((size_t)L, nullptr);
+    c->gact.assign((size_t)L, nullptr);
+    c->w.assign((size_t)3 * L, nullptr);
+    c->gw.assign((size_t)3 * L, nullptr);
+    for (int32_t l = 0; l < L; ++l) {
+        c->act[(size_t)l] = (float*)act[l];
+        c->gact[(size_t)l] = (float*)grad_act[l];
+        for (int j = 0; j < 3; ++j) {
+            c->w[(size_t)(3 * l + j)] = (const float*)weights[3 * l + j];
+            c->gw[(size_t)(3 * l + j)] = (float*)grad_w[3 * l + j];
+        }
+    }
+    c->labels = labels;
+    c->mask = train_mask;
+    c->staging = (char*)staging;
+    c->scratch = (char*)scratch;
+    c->bound = true;
+    c->staged_layer = c->staged_p = -1;
+    c->loss_done = false;
+    std::fill(c->fwd_done.begin(), c->fwd_done.end(), 0);
+    std::fill(c->bwd_done.begin(), c->bwd_done.end(), 0);
+    return GNN_OK;
+}
+
+gnn_status gnn_permute_rows(gnn_ctx* c, const void* src, void* dst, int64_t row_bytes,
+                            int32_t to_library_order, void* stream)
+{
+    if (!c) return GNN_EINVAL;
+    if (!c->built) return c->fail(GNN_ESTATE, "no partitions built");
+    if (!src || !dst || row_bytes < 1 || src == dst) return c->fail(GNN_EINVAL, "bad permute arguments");
+    gnn_status st = ensure_device(c);
+    if (st != GNN_OK) return st;
+    hipStream_t s = (hipStream_t)stream;
+    if (to_library_order) launch_gather_rows(src, c->D.order, dst, c->M.n, row_bytes, s);
+    else launch_scatter_rows(src, c->D.order, dst, c->M.n, row_bytes, s);
+    return check_launch(c, "gnn_permute_rows");
+}
+
+gnn_status gnn_gather_boundary(gnn_ctx* c, int32_t layer, int32_t p, void* stream)
+{
+    if (!c) return GNN_EINVAL;
+    gnn_status st = check_lp(c, layer, p);
+    if (st != GNN_OK) return st;
+    hipStream_t s = (hipStream_t)stream;
+    const HostMeta& M = c->M;
+    const int64_t b0 = M.boff[(size_t)p], nb = M.boff[(size_t)p + 1] - b0;
+    const int64_t row_bytes = (int64_t)c->dims[(size_t)layer - 1] * 4;
+    {
+        Timed t(c, s, GNN_K_GATHER);
+        launch_gather_rows(c->layer_input(layer), c->D.bnd + b0, c->staging, nb, row_bytes, s);
+    }
+    c->staged_layer = layer;
+    c->staged_p = p;
+    return check_launch(c, "gnn_gather_boundary");
+}
+
+gnn_status gnn_layer_fwd(gnn_ctx* c, int32_t layer, int32_t p, void* stream)
+{
+    if (!c) return GNN_EINVAL;
+    gnn_status st = check_lp(c, layer, p);
+    if (st != GNN_OK) return st;
+    if (c->staged_layer != layer || c->staged_p != p)
+        return c->fail(GNN_ESTATE, "staging does not hold this (layer, partition); call gnn_gather_boundary first");
+    hipStream_t s = (hipStream_t)stream;
+    const HostMeta& M = c->M;
+    const int64_t r0 = M.off[(size_t)p], np = M.off[(size_t)p + 1] - r0;
+    const int32_t din = c->dims[(size_t)layer - 1], dout = c->dims[(size_t)layer];
+    const float* in = c->layer_input(layer);
+    float* Z = (float*)(c->scratch + c->ws.z);
+    {
+        Timed t(c, s, GNN_K_SPMM);
+        run_spmm_fwd(c, layer, p, s);
+    }
+    {
+        Timed t(c, s, GNN_K_GEMM_FWD);
+        GemmSeg seg[2];
+        seg[0].a = Z; seg[0].lda = din; seg[0].b = c->w[(size_t)3 * (layer - 1)]; seg[0].ldb = dout; seg[0].k = din;
+        int nseg = 1;
+        if (c->model == GNN_SAGE_MEAN) {
+            seg[1].a = in + r0 * din; seg[1].lda = din;
+            seg[1].b = c->w[(size_t)3 * (layer - 1) + 1]; seg[1].ldb = dout; seg[1].k = din;
+            nseg = 2;
+        }
+        GemmEpilogue ep;
+        ep.bias = c->has_bias ? c->w[(size_t)3 * (layer - 1) + 2] : nullptr;
+        ep.relu = layer < c->L ? 1 : 0;
+        launch_gemm_nn(seg, nseg, c->act[(size_t)layer - 1] + r0 * dout, dout, np, dout, ep, s);
+    }
+    c->fwd_done[(size_t)(layer - 1) * (size_t)M.k + (size_t)p] = 1;
+    return check_launch(c, "gnn_layer_fwd");
+}
+
+gnn_status gnn_loss(gnn_ctx* c, void* stream)
+{
+    if (!c) return GNN_EINVAL;
+    if (!c->bound) return c->fail(GNN_ESTATE, "buffers are not bound (call gnn_bind)");
+    for (uint8_t f : c->fwd_done)
+        if (!f) return c->fail(GNN_ESTATE, "gnn_loss before the forward pass has covered every (layer, partition)");
+    hipStream_t s = (hipStream_t)stream;
+    float* scal = (float*)(c->scratch + c->ws.scalars);
+    {
+        Timed t(c, s, GNN_K_LOSS);
+        launch_loss(c->act[(size_t)c->L - 1], c->labels, c->mask, c->gact[(size_t)c->L - 1], c->M.n,
+                    c->dims[(size_t)c->L], (unsigned long long*)(scal + 16),
+                    (float*)(c->scratch + c->ws.losspart), scal, s);
+    }
+    c->loss_done = true;
+    std::fill(c->bwd_done.begin(), c->bwd_done.end(), 0);
+    return check_launch(c, "gnn_loss");
+}
+
+gnn_status gnn_read_loss(gnn_ctx* c, void* stream, float* loss_out)
+{
+    if (!c || !loss_out) return GNN_EINVAL;
+    if (!c->bound || !c->loss_done) return c->fail(GNN_ESTATE, "no loss has been computed");
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e = hipStreamSynchronize(s);
+    if (e == hipSuccess)
+        e = hipMemcpy(loss_out, c->scratch + c->ws.scalars, sizeof(float), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return c->fail(GNN_EHIP, std::string("gnn_read_loss: ") + hipGetErrorString(e));
+    return GNN_OK;
+}
+
+gnn_status gnn_layer_bwd(gnn_ctx* c, int32_t layer, int32_t p, void* stream)
+{
+    if (!c) return GNN_EINVAL;
+    gnn_status st = check_lp(c, layer, p);
+    if (st != GNN_OK) return st;
+    if (!c->loss_done) return c->fail(GNN_ESTATE, "gnn_layer_bwd before the forward pass and gnn_loss");
+    if (layer < c->L && c->bwd_done[(size_t)layer + 1] < c->M.k)
+        return c->fail(GNN_ESTATE, "the backward pass of layer+1 has not covered every partition");
+    if (c->staged_layer != layer || c->staged_p != p)
+        return c->fail(GNN_ESTATE, "staging does not hold this (layer, partition); call gnn_gather_boundary first");
+    hipStream_t s = (hipStream_t)stream;
+    const HostMeta& M = c->M;
+    const int32_t L = c->L;
+    const int64_t r0 = M.off[(size_t)p], np = M.off[(size_t)p + 1] - r0;
+    const int64_t nb = M.boff[(size_t)p + 1] - M.boff[(size_t)p];
+    const int32_t din = c->dims[(size_t)layer - 1], dout = c->dims[(size_t)layer];
+    const float* in = c->layer_input(layer);
+    const float* W = c->w[(size_t)3 * (layer - 1)];
+    const float* Ws = c->w[(size_t)3 * (layer - 1) + 1];
+    float* gW = c->gw[(size_t)3 * (layer - 1)];
+    float* gWs = c->gw[(size_t)3 * (layer - 1) + 1];
+    float* gb = c->has_bias ? c->gw[(size_t)3 * (layer - 1) + 2] : nullptr;
+    float* Z = (float*)(c->scratch + c->ws.z);
+    float* dYbuf = (float*)(c->scratch + c->ws.dy);
+    float* dZ = (float*)(c->scratch + c->ws.dz);
+    float* dGA = (float*)(c->scratch + c->ws.dga);
+    float* partial = (float*)(c->scratch + c->ws.partial);
+    float* colpart = (float*)(c->scratch + c->ws.colpart);
+
+    // write-back buffer initialisation: first partition of this layer since gnn_loss
+    if (layer >= 2 && c->bwd_done[(size_t)layer] == 0) {
+        Timed t(c, s, GNN_K_OTHER);
+        launch_fill_zero(c->gact[(size_t)layer - 2], M.n * (int64_t)din * 4, s);
+    }
+    // activation backward: dY = grad A ⊙ [A > 0] on hidden layers, grad A itself on the last
+    const float* g = c->gact[(size_t)layer - 1] + r0 * dout;
+    const float* dY = g;
+    {
+        Timed t(c, s, GNN_K_ACT_BWD);
+        if (layer < L) {
+            launch_act_bwd(g, c->act[(size_t)layer - 1] + r0 * dout, dYbuf, np, dout, gb, colpart, s);
+            dY = dYbuf;
+        } else {
+            launch_act_bwd(g, nullptr, nullptr, np, dout, gb, colpart, s);
+        }
+    }
+    // recompute the aggregate from the regathered rows
+    {
+        Timed t(c, s, GNN_K_SPMM);
+        run_spmm_fwd(c, layer, p, s);
+    }
+    // weight gradients, summed over partitions
+    {
+        Timed t(c, s, GNN_K_GEMM_DW);
+        launch_gemm_tn(Z, din, dY, dout, gW, dout, din, dout, np, partial, s);
+        if (c->model == GNN_SAGE_MEAN)
+            launch_gemm_tn(in + r0 * din, din, dY, dout, gWs, dout, din, dout, np, partial, s);
+    }
+    if (layer >= 2) {
+        float* gprev = c->gact[(size_t)layer - 2];
+        {
+            Timed t(c, s, GNN_K_GEMM_DZ);
+            GemmEpilogue ep;
+            launch_gemm_nt(dY, dout, W, dout, dZ, din, np, din, dout, ep, s);
+        }
+        {
+            Timed t(c, s, GNN_K_SPMM_T);
+            const int64_t t0 = M.toff[(size_t)p];
+            launch_spmm(c->D.trp + t0, c->D.tcol, c->D.tw, nullptr, dZ, np, nullptr, dGA, np + nb, din, s);
+        }
+        {
+            Timed t(c, s, GNN_K_SCATTER);
+            launch_scatter_add(dGA, np + nb, np, r0, c->D.bnd + M.boff[(size_t)p], gprev, din, s);
+        }
+        if (c->model == GNN_SAGE_MEAN) {
+            Timed t(c, s, GNN_K_GEMM_DZ);
+            GemmEpilogue ep;
+            ep.accumulate = 1;
+            launch_gemm_nt(dY, dout, Ws, dout, gprev + r0 * din, din, np, din, dout, ep, s);
+        }
+    }
+    c->bwd_done[(size_t)layer] += 1;
+    return check_launch(c, "gnn_layer_bwd");
+}
+
+gnn_status gnn_epoch(gnn_ctx* c, void* stream, float* loss_out)
+{
+    if (!c || !loss_out) return GNN_EINVAL;
+    if (!c->bound) return c->fail(GNN_ESTATE, "buffers are not bound (call gnn_bind)");
+    hipStream_t s = (hipStream_t)stream;
+    const int32_t L = c->L, k = c->M.k;
+    c->events_used = 0;
+    gnn_status st;
+    {
+        Timed t(c, s, GNN_K_OTHER);
+        for (int32_t l = 0; l < L; ++l) {
+            const int64_t wsz = (int64_t)c->dims[(size_t)l] * c->dims[(size_t)l + 1] * 4;
+            launch_fill_zero(c->gw[(size_t)3 * l], wsz, s);
+            if (c->model == GNN_SAGE_MEAN) launch_fill_zero(c->gw[(size_t)3 * l + 1], wsz, s);
+            if (c->has_bias) launch_fill_zero(c->gw[(size_t)3 * l + 2], (int64_t)c->dims[(size_t)l + 1] * 4, s);
+        }
+    }
+    for (int32_t l = 1; l <= L; ++l)
+        for (int32_t p = 0; p < k; ++p) {
+            if ((st = gnn_gather_boundary(c, l, p, stream)) != GNN_OK) return st;
+            if ((st = gnn_layer_fwd(c, l, p, stream)) != GNN_OK) return st;
+        }
+    if ((st = gnn_loss(c, stream)) != GNN_OK) return st;
+    for (int32_t l = L; l >= 1; --l)
+        for (int32_t p = 0; p < k; ++p) {
+            if ((st = gnn_gather_boundary(c, l, p, stream)) != GNN_OK) return st;
+            if ((st = gnn_layer_bwd(c, l, p, stream)) != GNN_OK) return st;
+        }
+    if ((st = gnn_read_loss(c, stream, loss_out)) != GNN_OK) return st;
+    if (c->prof) collect_profile(c);
+    return GNN_OK;
+}
+
+gnn_status gnn_set_profiling(gnn_ctx* c, int32_t enabled)
+{
+    if (!c) return GNN_EINVAL;
+    c->prof = enabled != 0;
+    c->events_used = 0;
+    return GNN_OK;
+}
+
+gnn_status gnn_get_profile(const gnn_ctx* c, double* ms, int64_t* launches)
+{
+    if (!c || !ms || !launches) return GNN_EINVAL;
+    for (int i = 0; i < GNN_K_COUNT; ++i) {
+        ms[i] = c->prof_ms[i];
+        launches[i] = c->prof_launches[i];
+    }
+    return GNN_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,109 @@
+// Internal declarations shared by the host code and the kernel launchers of libgnnmi.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "gnnmi.h"
+
+namespace gnnmi {
+
+// Host-side partition metadata.  "row" always means a vertex in library order
+// (partition-major, ascending original id inside a partition).
+struct HostMeta {
+    int64_t n = 0;
+    int32_t k = 0;
+    int model = 0;
+    std::vector<int32_t> part;      // original id -> partition
+    std::vector<int32_t> order;     // row -> original id
+    std::vector<int32_t> newid;     // original id -> row
+    std::vector<int64_t> off;       // k+1, first row of each partition
+    // aggregation operator S, rows in library order; partition p owns entries
+    // [rp[off[p]], rp[off[p+1]])
+    std::vector<int64_t> rp;        // n+1
+    std::vector<int32_t> lcol;      // local column: < n_p -> own row, else n_p + index into B_p
+    std::vector<float> ew;          // per-entry weight (GCN); empty for SAGE
+    std::vector<float> rscale;      // per-row scale applied after the sum (SAGE: 1/deg); empty for GCN
+    // boundary lists
+    std::vector<int64_t> boff;      // k+1
+    std::vector<int32_t> bnd;       // rows (library order), ascending inside a partition
+    std::vector<int32_t> bnd_orig;  // same entries as original ids
+    // transpose of S per partition: rows are the entries of R_p = [own_p ; B_p]
+    std::vector<int64_t> toff;      // k+1, offset of partition p's rows in trp
+    std::vector<int64_t> trp;       // sum |R_p| + 1, positions into tcol / tw
+    std::vector<int32_t> tcol;      // local destination row (0 .. n_p)
+    std::vector<float> tw;          // weight of the entry (both models)
+    gnn_stats stats{};
+};
+
+// Builds everything above.  Returns GNN_OK or an error with `err` set.
+gnn_status build_host_meta(int model, int64_t n, const int64_t* rowptr, const int32_t* colidx,
+                           int32_t k, int32_t mode, uint64_t seed, const int32_t* user_part,
+                           HostMeta& out, std::string& err);
+
+// ---- kernel launchers (all enqueue on `s`; sizes already validated by the caller) --------
+
+// dst[i,:] = src[idx[i],:] for `rows` rows of row_bytes bytes.
+void launch_gather_rows(const void* src, const int32_t* idx, void* dst, int64_t rows,
+                        int64_t row_bytes, hipStream_t s);
+// dst[idx[i],:] = src[i,:]
+void launch_scatter_rows(const void* src, const int32_t* idx, void* dst, int64_t rows,
+                         int64_t row_bytes, hipStream_t s);
+
+// out[r,:] = rowscale[r] * sum_e w[e] * src(col[e])[:],  e in [rp[r], rp[r+1])
+// src(c) = a_rows + c*d if c < n_a else b_rows + (c - n_a)*d.  w / rowscale may be null (= 1).
+// rp points at the first row's entry of a global row-pointer array; col / w are indexed with
+// the absolute positions stored in rp.
+void launch_spmm(const int64_t* rp, const int32_t* col, const float* w, const float* rowscale,
+                 const float* a_rows, int64_t n_a, const float* b_rows, float* out,
+                 int64_t nrows, int32_t d, hipStream_t s);
+
+// dst[map(i),:] += src[i,:] with map(i) = base_row + i for i < n_own, idx[i - n_own] otherwise.
+void launch_scatter_add(const float* src, int64_t nrows, int64_t n_own, int64_t base_row,
+                        const int32_t* idx, float* dst, int32_t d, hipStream_t s);
+
+struct GemmSeg {          // one K-segment of a product: A_seg [M x K] times B_seg [K x N]
+    const float* a = nullptr;
+    int64_t lda = 0;
+    const float* b = nullptr;
+    int64_t ldb = 0;
+    int32_t k = 0;
+};
+struct GemmEpilogue {
+    const float* bias = nullptr;      // per column, may be null
+    int relu = 0;
+    int accumulate = 0;               // C += result instead of C = result
+};
+// C[M x N] = sum over segments A[m, k] (row-major, lda) * B[k, n] (row-major, ldb)
+void launch_gemm_nn(const GemmSeg* segs, int nseg, float* c, int64_t ldc, int64_t m, int32_t n,
+                    const GemmEpilogue& ep, hipStream_t s);
+// C[M x N] = A[M x K] * B^T with B stored [N x K] row-major
+void launch_gemm_nt(const float* a, int64_t lda, const float* b, int64_t ldb, float* c,
+                    int64_t ldc, int64_t m, int32_t n, int32_t k, const GemmEpilogue& ep,
+                    hipStream_t s);
+// C[M x N] += A^T B with A stored [K x M], B stored [K x N] (K = number of vertices, large):
+// split over K into `splits` partial products in `partial`, then reduced in a fixed order.
+int gemm_tn_splits(int64_t kdim, int32_t m, int32_t n);
+void launch_gemm_tn(const float* a, int64_t lda, const float* b, int64_t ldb, float* c,
+                    int64_t ldc, int32_t m, int32_t n, int64_t kdim, float* partial,
+                    hipStream_t s);
+
+// dy = g * (act > 0) (or dy = g when act == null); colsum partials then gb += colsum.
+// `partial` holds ceil(rows / 64) * d floats.
+void launch_act_bwd(const float* g, const float* act, float* dy, int64_t rows, int32_t d,
+                    float* gb, float* partial, hipStream_t s);
+int64_t act_bwd_partial_floats(int64_t rows, int32_t d);
+
+// softmax cross-entropy over masked rows; grad[n, c]; *loss_dev = mean loss.  count_dev
+// receives |M| (counted on the device in the same call).
+void launch_loss(const float* logits, const int32_t* labels, const uint8_t* mask, float* grad,
+                 int64_t n, int32_t c, unsigned long long* count_dev, float* partial,
+                 float* loss_dev, hipStream_t s);
+int64_t loss_partial_floats(int64_t n);
+
+void launch_fill_zero(void* p, int64_t bytes, hipStream_t s);
+
+}  // namespace gnnmi

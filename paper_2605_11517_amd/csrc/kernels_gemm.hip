@@ -1,0 +1,341 @@
+// Dense contractions of the path on the fp32 matrix cores (v_mfma_f32_32x32x2_f32), gfx950.
+//
+//   forward   A_p^l  = act( Z_p W^l (+ X_p W_s^l) + b^l )        [n_p x d_in] [d_in x d_out]
+//   backward  dZ_p   = dY_p (W^l)^T                              [n_p x d_out][d_out x d_in]
+//             grad W^l += Z_p^T dY_p                             reduction over the n_p rows
+//
+// One workgroup of 4 wavefronts (2 x 2) owns a BM x BN tile of C.  K is walked in steps of 16
+// through a double-buffered LDS stage; operands are stored in LDS k-major ([k][m] and [k][n])
+// so that the 32 lanes feeding one MFMA operand column read 32 consecutive floats.  Widths
+// that are not multiples of 4 floats (e.g. 47 classes) take a scalar-load variant of the same
+// kernel; tails in M, N and K are zero-filled in LDS, never in memory.
+#include "gnn_internal.h"
+
+namespace gnnmi {
+namespace {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int kThreads = 256;
+constexpr int BK = 16;
+constexpr int PAD = 4;
+
+struct Operand {         // a matrix operand restricted to one K segment
+    const float* p;
+    int64_t ld;
+};
+
+// Tile whose k index is the contiguous one in memory: (slow = m or n, fast = k).
+// Thread t covers slow = t / 4 + 64 i, k = 4 (t % 4) .. + 3.
+template <int BT, bool VEC>
+__device__ inline void load_kfast(const float* __restrict__ p, int64_t ld, int64_t slow0,
+                                  int64_t nslow, int32_t k0, int32_t kend, float4 (&r)[BT / 64])
+{
+    const int t = threadIdx.x;
+    const int kq = (t & 3) * 4;
+#pragma unroll
+    for (int i = 0; i < BT / 64; ++i) {
+        const int64_t sidx = slow0 + (t >> 2) + 64 * i;
+        const int32_t k = k0 + kq;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (sidx < nslow) {
+            const float* q = p + sidx * ld + k;
+            if (VEC) {
+                if (k < kend) v = *reinterpret_cast<const float4*>(q);
+            } else {
+                if (k + 0 < kend) v.x = q[0];
+                if (k + 1 < kend) v.y = q[1];
+                if (k + 2 < kend) v.z = q[2];
+                if (k + 3 < kend) v.w = q[3];
+            }
+        }
+        r[i] = v;
+    }
+}
+template <int BT>
+__device__ inline void store_kfast(float (*S)[BT + PAD], const float4 (&r)[BT / 64])
+{
+    const int t = threadIdx.x;
+    const int kq = (t & 3) * 4;
+#pragma unroll
+    for (int i = 0; i < BT / 64; ++i) {
+        const int x = (t >> 2) + 64 * i;
+        S[kq + 0][x] = r[i].x;
+        S[kq + 1][x] = r[i].y;
+        S[kq + 2][x] = r[i].z;
+        S[kq + 3][x] = r[i].w;
+    }
+}
+
+// Tile whose m (or n) index is the contiguous one: (slow = k, fast = m or n).
+// Thread t covers k = t / (BT/4) + (1024/BT) i, fast = 4 (t % (BT/4)) .. + 3.
+template <int BT, bool VEC>
+__device__ inline void load_kslow(const float* __restrict__ p, int64_t ld, int64_t k0, int64_t kend,
+                                  int64_t fast0, int64_t nfast, float4 (&r)[BT / 64])
+{
+    constexpr int TPR = BT / 4;           // threads per k row
+    constexpr int KPP = kThreads / TPR;   // k rows per pass
+    const int t = threadIdx.x;
+    const int fq = (t % TPR) * 4;
+#pragma unroll
+    for (int i = 0; i < BT / 64; ++i) {
+        const int64_t k = k0 + t / TPR + KPP * i;
+        const int64_t f = fast0 + fq;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (k < kend) {
+            const float* q = p + k * ld + f;
+            if (VEC) {
+                if (f < nfast) v = *reinterpret_cast<const float4*>(q);
+            } else {
+                if (f + 0 < nfast) v.x = q[0];
+                if (f + 1 < nfast) v.y = q[1];
+                if (f + 2 < nfast) v.z = q[2];
+                if (f + 3 < nfast) v.w = q[3];
+            }
+        }
+        r[i] = v;
+    }
+}
+template <int BT>
+__device__ inline void store_kslow(float (*S)[BT + PAD], const float4 (&r)[BT / 64])
+{
+    constexpr int TPR = BT / 4;
+    constexpr int KPP = kThreads / TPR;
+    const int t = threadIdx.x;
+    const int fq = (t % TPR) * 4;
+#pragma unroll
+    for (int i = 0; i < BT / 64; ++i)
+        *reinterpret_cast<float4*>(&S[t / TPR + KPP * i][fq]) = r[i];
+}
+
+struct GemmArgs {
+    Operand a[2], b[2];      // up to two K segments
+    int32_t kseg[2];         // K of each segment (second may be 0)
+    float* c;
+    int64_t ldc;
+    int64_t m;               // rows of C
+    int32_t n;               // columns of C
+    const float* bias;
+    int32_t relu;
+    int32_t accumulate;
+    int64_t split_chunk;     // K per split (multiple of BK); 0 = no split
+    int64_t split_stride;    // elements between the partial C of consecutive splits
+};
+
+// A_KFAST: A(m,k) = a[m*lda + k]   (else a[k*lda + m])
+// B_KFAST: B(k,n) = b[n*ldb + k]   (else b[k*ldb + n])
+template <int BM, int BN, bool A_KFAST, bool B_KFAST, bool VEC>
+__global__ __launch_bounds__(kThreads) void k_gemm(const GemmArgs g)
+{
+    constexpr int WM = BM / 2, WN = BN / 2;   // wave tile
+    constexpr int TM = WM / 32, TN = WN / 32; // 32x32 MFMA tiles per wave
+    __shared__ float As[2][BK][BM + PAD];
+    __shared__ float Bs[2][BK][BN + PAD];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int wm0 = (wave >> 1) * WM, wn0 = (wave & 1) * WN;
+    const int64_t m0 = (int64_t)blockIdx.x * BM;
+    const int32_t n0 = blockIdx.y * BN;
+
+    // K range of this workgroup (split-K only with a single segment)
+    int64_t kbeg = 0, kend0 = g.kseg[0];
+    float* cbase = g.c;
+    if (g.split_chunk > 0) {
+        kbeg = (int64_t)blockIdx.z * g.split_chunk;
+        kend0 = kbeg + g.split_chunk < kend0 ? kbeg + g.split_chunk : kend0;
+        cbase += (int64_t)blockIdx.z * g.split_stride;
+    }
+    const int64_t tiles0 = kend0 > kbeg ? (kend0 - kbeg + BK - 1) / BK : 0;
+    const int64_t tiles1 = (g.kseg[1] + BK - 1) / BK;
+    const int64_t ntiles = tiles0 + tiles1;
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    float4 ra[BM / 64], rb[BN / 64];
+    auto load_tile = [&](int64_t t) {
+        const int seg = t < tiles0 ? 0 : 1;
+        const int64_t k0 = seg == 0 ? kbeg + t * BK : (t - tiles0) * BK;
+        const int64_t kend = seg == 0 ? kend0 : (int64_t)g.kseg[1];
+        if (A_KFAST) load_kfast<BM, VEC>(g.a[seg].p, g.a[seg].ld, m0, g.m, (int32_t)k0, (int32_t)kend, ra);
+        else load_kslow<BM, VEC>(g.a[seg].p, g.a[seg].ld, k0, kend, m0, g.m, ra);
+        if (B_KFAST) load_kfast<BN, VEC>(g.b[seg].p, g.b[seg].ld, n0, g.n, (int32_t)k0, (int32_t)kend, rb);
+        else load_kslow<BN, VEC>(g.b[seg].p, g.b[seg].ld, k0, kend, n0, g.n, rb);
+    };
+    auto store_tile = [&](int buf) {
+        if (A_KFAST) store_kfast<BM>(As[buf], ra); else store_kslow<BM>(As[buf], ra);
+        if (B_KFAST) store_kfast<BN>(Bs[buf], rb); else store_kslow<BN>(Bs[buf], rb);
+    };
+
+    if (ntiles > 0) {
+        load_tile(0);
+        store_tile(0);
+    }
+    __syncthreads();
+    for (int64_t t = 0; t < ntiles; ++t) {
+        const int buf = (int)(t & 1);
+        if (t + 1 < ntiles) load_tile(t + 1);
+        const int kl = lane >> 5, xl = lane & 31;
+#pragma unroll
+        for (int kk = 0; kk < BK; kk += 2) {
+            float av[TM], bv[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) av[i] = As[buf][kk + kl][wm0 + 32 * i + xl];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) bv[j] = Bs[buf][kk + kl][wn0 + 32 * j + xl];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
+        }
+        if (t + 1 < ntiles) store_tile(buf ^ 1);
+        __syncthreads();
+    }
+
+    // epilogue: lane holds C[8 (r/4) + 4 (lane/32) + r%4][lane%32] of each 32x32 tile
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int32_t col = n0 + wn0 + 32 * j + (lane & 31);
+            if (col >= g.n) continue;
+            const float bv = g.bias ? g.bias[col] : 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int64_t row = m0 + wm0 + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                if (row >= g.m) continue;
+                float v = acc[i][j][r] + bv;
+                if (g.relu) v = v > 0.f ? v : 0.f;
+                float* dst = cbase + row * g.ldc + col;
+                if (g.accumulate) v += *dst;
+                *dst = v;
+            }
+        }
+}
+
+// c[i] += sum_s partial[s * stride + i], s ascending
+__global__ __launch_bounds__(256) void k_reduce_partials(const float* __restrict__ partial,
+                                                         int32_t splits, int64_t stride,
+                                                         float* __restrict__ c, int64_t ldc,
+                                                         int32_t m, int32_t n)
+{
+    const int64_t total = (int64_t)m * n;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total;
+         i += (int64_t)gridDim.x * 256) {
+        float s = 0.f;
+        for (int32_t z = 0; z < splits; ++z) s += partial[(int64_t)z * stride + i];
+        const int64_t r = i / n, cc = i - r * n;
+        c[r * ldc + cc] += s;
+    }
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+template <bool A_KFAST, bool B_KFAST>
+void launch_gemm(const GemmArgs& g, int splits, hipStream_t s)
+{
+    if (g.m <= 0 || g.n <= 0) return;
+    // float4 loads need 16-byte aligned rows, and the contiguous index of each operand (k for a
+    // k-fast operand, m or n otherwise) must consist of whole float4s
+    bool vec = true;
+    for (int i = 0; i < 2; ++i) {
+        if (g.kseg[i] == 0) continue;
+        vec = vec && aligned16(g.a[i].p) && aligned16(g.b[i].p) && g.a[i].ld % 4 == 0 &&
+              g.b[i].ld % 4 == 0;
+        if (A_KFAST || B_KFAST) vec = vec && g.kseg[i] % 4 == 0;
+    }
+    if (!A_KFAST) vec = vec && g.m % 4 == 0;
+    if (!B_KFAST) vec = vec && g.n % 4 == 0;
+    const bool big_m = g.m > 64, big_n = g.n > 64;
+#define GNN_GEMM(BM, BN, VEC)                                                                   \
+    hipLaunchKernelGGL((k_gemm<BM, BN, A_KFAST, B_KFAST, VEC>),                                 \
+                       dim3((unsigned)((g.m + BM - 1) / BM), (unsigned)((g.n + BN - 1) / BN),   \
+                            (unsigned)splits),                                                  \
+                       dim3(kThreads), 0, s, g)
+    if (vec) {
+        if (big_m && big_n) GNN_GEMM(128, 128, true);
+        else if (big_m) GNN_GEMM(128, 64, true);
+        else if (big_n) GNN_GEMM(64, 128, true);
+        else GNN_GEMM(64, 64, true);
+    } else {
+        if (big_m && big_n) GNN_GEMM(128, 128, false);
+        else if (big_m) GNN_GEMM(128, 64, false);
+        else if (big_n) GNN_GEMM(64, 128, false);
+        else GNN_GEMM(64, 64, false);
+    }
+#undef GNN_GEMM
+}
+
+}  // namespace
+
+void launch_gemm_nn(const GemmSeg* segs, int nseg, float* c, int64_t ldc, int64_t m, int32_t n,
+                    const GemmEpilogue& ep, hipStream_t s)
+{
+    GemmArgs g{};
+    for (int i = 0; i < 2; ++i) {
+        if (i < nseg) {
+            g.a[i] = {segs[i].a, segs[i].lda};
+            g.b[i] = {segs[i].b, segs[i].ldb};
+            g.kseg[i] = segs[i].k;
+        } else {
+            g.a[i] = g.a[0];
+            g.b[i] = g.b[0];
+            g.kseg[i] = 0;
+        }
+    }
+    g.c = c; g.ldc = ldc; g.m = m; g.n = n;
+    g.bias = ep.bias; g.relu = ep.relu; g.accumulate = ep.accumulate;
+    launch_gemm<true, false>(g, 1, s);
+}
+
+void launch_gemm_nt(const float* a, int64_t lda, const float* b, int64_t ldb, float* c,
+                    int64_t ldc, int64_t m, int32_t n, int32_t k, const GemmEpilogue& ep,
+                    hipStream_t s)
+{
+    GemmArgs g{};
+    g.a[0] = g.a[1] = {a, lda};
+    g.b[0] = g.b[1] = {b, ldb};
+    g.kseg[0] = k; g.kseg[1] = 0;
+    g.c = c; g.ldc = ldc; g.m = m; g.n = n;
+    g.bias = ep.bias; g.relu = ep.relu; g.accumulate = ep.accumulate;
+    launch_gemm<true, true>(g, 1, s);
+}
+
+int gemm_tn_splits(int64_t kdim, int32_t m, int32_t n)
+{
+    const int64_t tiles = (int64_t)((m + 127) / 128) * ((n + 127) / 128);
+    int64_t want = (1024 + tiles - 1) / tiles;          // ~4 workgroups per CU
+    int64_t most = (kdim + 16 * BK - 1) / (16 * BK);    // at least 16 k-steps per split
+    int64_t sp = want < most ? want : most;
+    return (int)(sp < 1 ? 1 : sp);
+}
+
+void launch_gemm_tn(const float* a, int64_t lda, const float* b, int64_t ldb, float* c,
+                    int64_t ldc, int32_t m, int32_t n, int64_t kdim, float* partial,
+                    hipStream_t s)
+{
+    if (kdim <= 0 || m <= 0 || n <= 0) return;
+    const int splits = gemm_tn_splits(kdim, m, n);
+    int64_t chunk = (kdim + splits - 1) / splits;
+    chunk = (chunk + BK - 1) / BK * BK;
+    GemmArgs g{};
+    g.a[0] = g.a[1] = {a, lda};
+    g.b[0] = g.b[1] = {b, ldb};
+    g.kseg[0] = (int32_t)kdim; g.kseg[1] = 0;
+    g.c = partial; g.ldc = n; g.m = m; g.n = n;
+    g.split_chunk = chunk;
+    g.split_stride = (int64_t)m * n;
+    launch_gemm<false, false>(g, splits, s);
+    int64_t blocks = ((int64_t)m * n + 255) / 256;
+    hipLaunchKernelGGL(k_reduce_partials, dim3((unsigned)(blocks > 1024 ? 1024 : blocks)), dim3(256),
+                       0, s, (const float*)partial, splits, (int64_t)m * n, c, ldc, m, n);
+}
+
+}  // namespace gnnmi

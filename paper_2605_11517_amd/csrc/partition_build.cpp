@@ -1,0 +1,359 @@
+// Host-side construction of the partition metadata: assignment rules, library vertex order,
+// boundary lists, per-partition local topology T_p and its transpose, normalisation factors.
+//
+// Paper passages this follows:
+//   - a partition's input GA_p is the union of the sources of its destinations
+//     (Cache-(Re)Gather-Bypass section, "(Re)gather");
+//   - neighbours are ordered by partition id, then vertex id, so that a gather touches each
+//     source partition as one ascending run (appendix "In-Partition Vertex Ordering for
+//     Sequential Accesses");
+//   - label propagation towards the partition holding most neighbours, with the size penalty
+//     |P_j| / (1.1 |V| / k) and a capacity limit per partition (partitioning section and its
+//     appendix).
+#include <algorithm>
+#include <atomic>
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <functional>
+#include <new>
+#include <thread>
+
+#include "gnn_internal.h"
+
+namespace gnnmi {
+namespace {
+
+int worker_count()
+{
+    int t = (int)std::thread::hardware_concurrency();
+    if (const char* e = std::getenv("GNNMI_THREADS")) t = std::atoi(e);
+    return std::max(1, std::min(t, 16));
+}
+
+// Calls fn(tid, index) for every index in [0, count), handing out chunks dynamically.
+void parallel_for(int64_t count, int64_t chunk, const std::function<void(int, int64_t)>& fn)
+{
+    int nt = (int)std::min<int64_t>(worker_count(), std::max<int64_t>(1, (count + chunk - 1) / chunk));
+    if (nt <= 1) {
+        for (int64_t i = 0; i < count; ++i) fn(0, i);
+        return;
+    }
+    std::atomic<int64_t> next{0};
+    std::atomic<int> failed{0};  // an allocation failure in a worker is re-raised by the caller
+    std::vector<std::thread> pool;
+    for (int t = 0; t < nt; ++t)
+        pool.emplace_back([&, t] {
+            try {
+                for (;;) {
+                    int64_t lo = next.fetch_add(chunk);
+                    if (lo >= count || failed.load(std::memory_order_relaxed)) break;
+                    int64_t hi = std::min(count, lo + chunk);
+                    for (int64_t i = lo; i < hi; ++i) fn(t, i);
+                }
+            } catch (...) {
+                failed.store(1);
+            }
+        });
+    for (auto& th : pool) th.join();
+    if (failed.load()) throw std::bad_alloc();
+}
+
+inline uint64_t splitmix64(uint64_t x)
+{
+    uint64_t z = x + 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+// Rank vertices by (hash, id); rank r goes to partition r mod k.
+void assign_random(int64_t n, int32_t k, uint64_t seed, std::vector<int32_t>& part)
+{
+    std::vector<std::pair<uint64_t, int32_t>> keys((size_t)n);
+    parallel_for(n, 1 << 16, [&](int, int64_t v) {
+        keys[(size_t)v] = {splitmix64(seed ^ splitmix64((uint64_t)v)), (int32_t)v};
+    });
+    std::sort(keys.begin(), keys.end());
+    part.resize((size_t)n);
+    for (int64_t r = 0; r < n; ++r) part[(size_t)keys[(size_t)r].second] = (int32_t)(r % k);
+}
+
+// One synchronous label-propagation round: targets from the frozen state, then an ascending
+// sweep that honours the capacity at the moment of each move.
+void lp_round(int64_t n, const int64_t* rowptr, const int32_t* colidx, int32_t k,
+              std::vector<int32_t>& part)
+{
+    std::vector<int64_t> sizes((size_t)k, 0);
+    for (int64_t v = 0; v < n; ++v) sizes[(size_t)part[(size_t)v]]++;
+    // smallest partition, lowest id among equals: the best of all partitions holding no
+    // neighbour of a vertex
+    int32_t jmin = 0;
+    for (int32_t j = 1; j < k; ++j)
+        if (sizes[(size_t)j] < sizes[(size_t)jmin]) jmin = j;
+
+    std::vector<int32_t> target((size_t)n);
+    int nt = worker_count();
+    std::vector<std::vector<int64_t>> cnt((size_t)nt, std::vector<int64_t>((size_t)k, 0));
+    std::vector<std::vector<int32_t>> touched((size_t)nt);
+    parallel_for(n, 4096, [&](int tid, int64_t v) {
+        auto& c = cnt[(size_t)tid];
+        auto& tl = touched[(size_t)tid];
+        tl.clear();
+        int64_t deg = 0;
+        for (int64_t e = rowptr[v]; e < rowptr[v + 1]; ++e) {
+            int32_t u = colidx[e];
+            if (u == v) continue;
+            int32_t j = part[(size_t)u];
+            if (c[(size_t)j]++ == 0) tl.push_back(j);
+            ++deg;
+        }
+        int32_t cur = part[(size_t)v];
+        auto key = [&](int32_t j) {
+            return (int64_t)11 * n * c[(size_t)j] - (int64_t)10 * k * deg * sizes[(size_t)j];
+        };
+        int64_t best = key(jmin);
+        int32_t arg = jmin;
+        for (int32_t j : tl) {
+            int64_t kj = key(j);
+            if (kj > best || (kj == best && j < arg)) {
+                best = kj;
+                arg = j;
+            }
+        }
+        if (key(cur) == best) arg = cur;
+        target[(size_t)v] = arg;
+        for (int32_t j : tl) c[(size_t)j] = 0;
+    });
+
+    const int64_t cap = ((int64_t)11 * n) / ((int64_t)10 * k);
+    for (int64_t v = 0; v < n; ++v) {
+        int32_t j = target[(size_t)v], cur = part[(size_t)v];
+        if (j != cur && sizes[(size_t)j] < cap) {
+            sizes[(size_t)cur]--;
+            sizes[(size_t)j]++;
+            part[(size_t)v] = j;
+        }
+    }
+}
+
+}  // namespace
+
+gnn_status build_host_meta(int model, int64_t n, const int64_t* rowptr, const int32_t* colidx,
+                           int32_t k, int32_t mode, uint64_t seed, const int32_t* user_part,
+                           HostMeta& M, std::string& err)
+{
+    if (!rowptr || n < 1) { err = "n must be >= 1 and rowptr non-null"; return GNN_EINVAL; }
+    if (n > 0x7FFFFFF0ll) { err = "n exceeds the int32 vertex id range"; return GNN_EINVAL; }
+    if (k < 1 || (int64_t)k > n) { err = "k must satisfy 1 <= k <= n"; return GNN_EINVAL; }
+    if (mode != GNN_PART_USER && mode != GNN_PART_RANDOM && mode != GNN_PART_LP) {
+        err = "unknown partition mode"; return GNN_EINVAL;
+    }
+    if (mode == GNN_PART_USER && !user_part) { err = "user_part is null"; return GNN_EINVAL; }
+    if (rowptr[0] != 0) { err = "rowptr[0] must be 0"; return GNN_EINVAL; }
+    for (int64_t v = 0; v < n; ++v)
+        if (rowptr[v + 1] < rowptr[v]) { err = "rowptr is not monotone"; return GNN_EINVAL; }
+    const int64_t nnz_in = rowptr[n];
+    if (nnz_in > 0 && !colidx) { err = "colidx is null"; return GNN_EINVAL; }
+    {
+        std::atomic<int> bad{0};
+        parallel_for(n, 8192, [&](int, int64_t v) {
+            int64_t prev = -1;
+            for (int64_t e = rowptr[v]; e < rowptr[v + 1]; ++e) {
+                int64_t u = colidx[e];
+                if (u < 0 || u >= n || u <= prev) bad.store(1, std::memory_order_relaxed);
+                prev = u;
+            }
+        });
+        if (bad.load()) {
+            err = "colidx must lie in [0, n) and ascend strictly inside every row";
+            return GNN_EINVAL;
+        }
+    }
+
+    try {
+        M = HostMeta{};
+        M.n = n;
+        M.k = k;
+        M.model = model;
+
+        // ---- assignment ----------------------------------------------------------------
+        if (mode == GNN_PART_USER) {
+            M.part.assign(user_part, user_part + n);
+            for (int64_t v = 0; v < n; ++v)
+                if (M.part[(size_t)v] < 0 || M.part[(size_t)v] >= k) {
+                    err = "user_part entry outside [0, k)";
+                    return GNN_EINVAL;
+                }
+        } else {
+            assign_random(n, k, seed, M.part);
+            if (mode == GNN_PART_LP)
+                for (int round = 0; round < 10; ++round) lp_round(n, rowptr, colidx, k, M.part);
+        }
+
+        // ---- library order: partition-major, ascending original id inside ----------------
+        M.off.assign((size_t)k + 1, 0);
+        for (int64_t v = 0; v < n; ++v) M.off[(size_t)M.part[(size_t)v] + 1]++;
+        for (int32_t p = 0; p < k; ++p) M.off[(size_t)p + 1] += M.off[(size_t)p];
+        M.order.resize((size_t)n);
+        M.newid.resize((size_t)n);
+        {
+            std::vector<int64_t> cur(M.off.begin(), M.off.end() - 1);
+            for (int64_t v = 0; v < n; ++v) {
+                int64_t r = cur[(size_t)M.part[(size_t)v]]++;
+                M.order[(size_t)r] = (int32_t)v;
+                M.newid[(size_t)v] = (int32_t)r;
+            }
+        }
+
+        // ---- operator rows: A + I for GCN (one self-loop each), A for SAGE ----------------
+        const bool gcn = (model == GNN_GCN);
+        std::vector<int32_t> opdeg((size_t)n);       // by original id
+        std::vector<uint8_t> add_self((size_t)n, 0);  // by original id
+        parallel_for(n, 8192, [&](int, int64_t v) {
+            int64_t len = rowptr[v + 1] - rowptr[v];
+            if (gcn) {
+                const int32_t* b = colidx + rowptr[v];
+                bool has = std::binary_search(b, b + len, (int32_t)v);
+                add_self[(size_t)v] = has ? 0 : 1;
+                len += has ? 0 : 1;
+            }
+            opdeg[(size_t)v] = (int32_t)len;
+        });
+        M.rp.assign((size_t)n + 1, 0);
+        for (int64_t r = 0; r < n; ++r)
+            M.rp[(size_t)r + 1] = M.rp[(size_t)r] + opdeg[(size_t)M.order[(size_t)r]];
+        const int64_t nnz = M.rp[(size_t)n];
+        M.lcol.resize((size_t)nnz);
+        if (gcn) M.ew.resize((size_t)nnz);
+        else {
+            M.rscale.resize((size_t)n);
+            for (int64_t r = 0; r < n; ++r) {
+                int32_t dg = opdeg[(size_t)M.order[(size_t)r]];
+                M.rscale[(size_t)r] = dg > 0 ? (float)(1.0 / (double)dg) : 0.0f;
+            }
+        }
+
+        // ---- phase A: boundary lists and local columns, partitions in parallel -----------
+        std::vector<std::vector<int32_t>> bnd_p((size_t)k);
+        const int nt = worker_count();
+        std::vector<std::vector<int32_t>> lmap((size_t)nt);  // row -> index in B_p, or -1
+        parallel_for(k, 1, [&](int tid, int64_t p) {
+            auto& map = lmap[(size_t)tid];
+            if (map.empty()) map.assign((size_t)n, -1);
+            const int64_t r0 = M.off[(size_t)p], r1 = M.off[(size_t)p + 1];
+            auto& B = bnd_p[(size_t)p];
+            for (int64_t r = r0; r < r1; ++r) {
+                int64_t v = M.order[(size_t)r];
+                for (int64_t e = rowptr[v]; e < rowptr[v + 1]; ++e) {
+                    int32_t ur = M.newid[(size_t)colidx[e]];
+                    if ((ur < r0 || ur >= r1) && map[(size_t)ur] < 0) {
+                        map[(size_t)ur] = 0;
+                        B.push_back(ur);
+                    }
+                }
+            }
+            std::sort(B.begin(), B.end());  // ascending row == (partition id, original id)
+            for (size_t i = 0; i < B.size(); ++i) map[(size_t)B[i]] = (int32_t)i;
+            const int32_t np = (int32_t)(r1 - r0);
+            std::vector<std::pair<int32_t, float>> row;
+            for (int64_t r = r0; r < r1; ++r) {
+                int64_t v = M.order[(size_t)r];
+                row.clear();
+                const double dv = (double)opdeg[(size_t)v];
+                auto push = [&](int64_t u) {
+                    int32_t ur = M.newid[(size_t)u];
+                    int32_t lc = (ur >= r0 && ur < r1) ? (int32_t)(ur - r0)
+                                                       : np + map[(size_t)ur];
+                    float w = gcn ? (float)(1.0 / std::sqrt((double)opdeg[(size_t)u] * dv)) : 1.0f;
+                    row.emplace_back(lc, w);
+                };
+                for (int64_t e = rowptr[v]; e < rowptr[v + 1]; ++e) push(colidx[e]);
+                if (gcn && add_self[(size_t)v]) push(v);
+                std::sort(row.begin(), row.end(),
+                          [](const std::pair<int32_t, float>& a, const std::pair<int32_t, float>& b) {
+                              return a.first < b.first;
+                          });
+                int64_t o = M.rp[(size_t)r];
+                for (auto& pr : row) {
+                    M.lcol[(size_t)o] = pr.first;
+                    if (gcn) M.ew[(size_t)o] = pr.second;
+                    ++o;
+                }
+            }
+            for (int32_t ur : B) map[(size_t)ur] = -1;
+        });
+        lmap.clear();
+        lmap.shrink_to_fit();
+
+        // ---- phase B: offsets --------------------------------------------------------------
+        M.boff.assign((size_t)k + 1, 0);
+        M.toff.assign((size_t)k + 1, 0);
+        for (int32_t p = 0; p < k; ++p) {
+            int64_t np = M.off[(size_t)p + 1] - M.off[(size_t)p];
+            M.boff[(size_t)p + 1] = M.boff[(size_t)p] + (int64_t)bnd_p[(size_t)p].size();
+            M.toff[(size_t)p + 1] = M.toff[(size_t)p] + np + (int64_t)bnd_p[(size_t)p].size();
+        }
+        M.bnd.resize((size_t)M.boff[(size_t)k]);
+        M.bnd_orig.resize((size_t)M.boff[(size_t)k]);
+        for (int32_t p = 0; p < k; ++p) {
+            int64_t o = M.boff[(size_t)p];
+            for (int32_t ur : bnd_p[(size_t)p]) {
+                M.bnd[(size_t)o] = ur;
+                M.bnd_orig[(size_t)o] = M.order[(size_t)ur];
+                ++o;
+            }
+            std::vector<int32_t>().swap(bnd_p[(size_t)p]);
+        }
+
+        // ---- phase C: transpose of every T_p ------------------------------------------------
+        M.trp.assign((size_t)M.toff[(size_t)k] + 1, 0);
+        M.tcol.resize((size_t)nnz);
+        M.tw.resize((size_t)nnz);
+        std::vector<int64_t> required((size_t)k, 0);
+        parallel_for(k, 1, [&](int, int64_t p) {
+            const int64_t r0 = M.off[(size_t)p], r1 = M.off[(size_t)p + 1];
+            const int64_t nR = M.toff[(size_t)p + 1] - M.toff[(size_t)p];
+            const int64_t e0 = M.rp[(size_t)r0], e1 = M.rp[(size_t)r1];
+            int64_t* trp = M.trp.data() + M.toff[(size_t)p];
+            std::vector<int64_t> cursor((size_t)nR + 1, 0);
+            for (int64_t e = e0; e < e1; ++e) cursor[(size_t)M.lcol[(size_t)e] + 1]++;
+            int64_t req = 0;
+            for (int64_t i = 0; i < nR; ++i) {
+                if (cursor[(size_t)i + 1] > 0) ++req;
+                cursor[(size_t)i + 1] += cursor[(size_t)i];
+            }
+            required[(size_t)p] = req;
+            for (int64_t i = 0; i < nR; ++i) trp[i] = e0 + cursor[(size_t)i];
+            if (p == k - 1) trp[nR] = e1;
+            for (int64_t r = r0; r < r1; ++r) {
+                const float rs = gcn ? 1.0f : M.rscale[(size_t)r];
+                for (int64_t e = M.rp[(size_t)r]; e < M.rp[(size_t)r + 1]; ++e) {
+                    int64_t pos = e0 + cursor[(size_t)M.lcol[(size_t)e]]++;
+                    M.tcol[(size_t)pos] = (int32_t)(r - r0);
+                    M.tw[(size_t)pos] = gcn ? M.ew[(size_t)e] : rs;
+                }
+            }
+        });
+
+        // ---- stats ---------------------------------------------------------------------------
+        gnn_stats& S = M.stats;
+        S.n = n;
+        S.nnz = nnz;
+        S.k = k;
+        S.sum_boundary = M.boff[(size_t)k];
+        for (int32_t p = 0; p < k; ++p) {
+            S.sum_required += required[(size_t)p];
+            S.max_own = std::max(S.max_own, M.off[(size_t)p + 1] - M.off[(size_t)p]);
+            S.max_boundary = std::max(S.max_boundary, M.boff[(size_t)p + 1] - M.boff[(size_t)p]);
+            S.max_nnz = std::max(S.max_nnz,
+                                 M.rp[(size_t)M.off[(size_t)p + 1]] - M.rp[(size_t)M.off[(size_t)p]]);
+        }
+    } catch (const std::bad_alloc&) {
+        err = "out of host memory while building partitions";
+        return GNN_ENOMEM;
+    }
+    return GNN_OK;
+}
+
+}  // namespace gnnmi

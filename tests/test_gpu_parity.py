@@ -1,0 +1,230 @@
+"""Parity of the HIP path with the CPU oracle, through the C ABI, on seeded inputs.
+
+Gate for floating point: per tensor, max |gpu - oracle| / max |oracle| <= 1e-4 (fp32 path).
+Gathered rows, partition assignment and boundary lists: bit-exact.
+"""
+import sys
+
+import numpy as np
+import pytest
+
+from helpers import empty_graph, rel_err, small_graph
+from oracle import fullgraph as og
+from oracle import partition as op
+from synth import features, glorot_weights, labels_and_mask, make_config
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-4
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def make_inputs(cfg, n, bias_scale=0.1):
+    dims = cfg["dims"]
+    X = features(n, dims[0], cfg["seed"])
+    y, m = labels_and_mask(n, dims[-1], cfg["train_frac"], cfg["seed"])
+    w = glorot_weights(dims, cfg["seed"], sage=(cfg["model"] == "sage"), bias_scale=bias_scale)
+    return X, y, m, w
+
+
+def compare(got, ref, model, has_bias=True, tol=TOL, tag=""):
+    worst = {}
+    keys = ["act", "gW", "gact"] + (["gb"] if has_bias else []) + (["gWs"] if model == "sage" else [])
+    for key in keys:
+        for l, (a, b) in enumerate(zip(got[key], ref[key])):
+            e = rel_err(a, b)
+            worst["%s[%d]" % (key, l)] = e
+    bad = {k: v for k, v in worst.items() if not (v <= tol)}
+    assert not bad, (tag, bad)
+    return worst
+
+
+def run_session(cfg, rowptr, colidx, X, y, m, w, k, mode, seed, has_bias=True, user_part=None):
+    from paper_2605_11517_amd import Session
+    s = Session(cfg["model"], cfg["dims"], rowptr, colidx, k, mode, seed, X, w, y, m,
+                has_bias=has_bias, user_part=user_part)
+    loss = s.epoch()
+    return s, loss
+
+
+@pytest.mark.parametrize("name", ["tiny", "mini_sage", "mini_gcn_directed"])
+def test_epoch_matches_oracle(name):
+    say("case epoch_matches_oracle %s" % name)
+    cfg, rowptr, colidx = make_config(name)
+    n = cfg["n"]
+    X, y, m, w = make_inputs(cfg, n)
+    ref = og.epoch(cfg["model"], rowptr, colidx, cfg["dims"], X, w, y, m)
+    s, loss = run_session(cfg, rowptr, colidx, X, y, m, w, cfg["k"], cfg["part"], cfg["seed"])
+    got = s.results()
+    assert abs(loss - ref["loss"]) <= TOL * abs(ref["loss"])
+    worst = compare(got, ref, cfg["model"], tag=name)
+    say("  worst rel err %.3g" % max(worst.values()))
+    # partition structure is bit-exact
+    part, k = s.ctx.get_partition()
+    want = (op.assign_random if cfg["part"] == "random" else
+            lambda n_, k_, s_: op.assign_lp(rowptr, colidx, k_, s_))(n, cfg["k"], cfg["seed"])
+    assert np.array_equal(part, want)
+
+
+@pytest.mark.parametrize("name", ["tiny", "mini_sage"])
+def test_gathered_rows_are_bit_exact(name):
+    say("case gathered_rows %s" % name)
+    import torch
+    cfg, rowptr, colidx = make_config(name)
+    n = cfg["n"]
+    X, y, m, w = make_inputs(cfg, n)
+    s, _ = run_session(cfg, rowptr, colidx, X, y, m, w, cfg["k"], cfg["part"], cfg["seed"])
+    part, k = s.ctx.get_partition()
+    ref = og.epoch(cfg["model"], rowptr, colidx, cfg["dims"], X, w, y, m, backward=False)
+    acts_gpu = [X] + [a for a in s.results()["act"]]
+    for layer in (1, 2):
+        d = cfg["dims"][layer - 1]
+        for p in range(k):
+            s.ctx.gather_boundary(layer, p, s.stream)
+            torch.cuda.synchronize()
+            b = op.boundary(rowptr, colidx, part, p)
+            assert np.array_equal(s.ctx.get_boundary(p), b)
+            staged = s.staging[: len(b) * d * 4].view(torch.float32).reshape(len(b), d).cpu().numpy()
+            if layer == 1:
+                # layer-0 rows are inputs: the gather must reproduce the oracle-side rows bit for bit
+                assert np.array_equal(staged.view(np.uint32), X[b].view(np.uint32))
+            else:
+                # deeper layers: a bit copy of the path's own activations, themselves within
+                # tolerance of the oracle's
+                assert np.array_equal(staged.view(np.uint32), acts_gpu[layer - 1][b].view(np.uint32))
+                assert rel_err(staged, ref["act"][layer - 2][b]) <= TOL
+
+
+def test_two_epochs_are_bit_identical_and_stepping_by_hand_equals_epoch():
+    say("case determinism + hand stepping")
+    import torch
+    cfg, rowptr, colidx = make_config("mini_sage")
+    n = cfg["n"]
+    X, y, m, w = make_inputs(cfg, n)
+    s, loss1 = run_session(cfg, rowptr, colidx, X, y, m, w, cfg["k"], cfg["part"], cfg["seed"])
+    r1 = s.results()
+    loss2 = s.epoch()
+    r2 = s.results()
+    assert loss1 == loss2
+    for key in ("act", "gact", "gW", "gWs", "gb"):
+        for a, b in zip(r1[key], r2[key]):
+            assert np.array_equal(a, b), key
+    # the same schedule issued call by call
+    c, st = s.ctx, s.stream
+    for g in s.gw:
+        if g is not None:
+            g.zero_()
+    L, k = s.L, c.k
+    for l in range(1, L + 1):
+        for p in range(k):
+            c.gather_boundary(l, p, st)
+            c.layer_fwd(l, p, st)
+    c.loss(st)
+    for l in range(L, 0, -1):
+        for p in range(k):
+            c.gather_boundary(l, p, st)
+            c.layer_bwd(l, p, st)
+    assert c.read_loss(st) == loss1
+    r3 = s.results()
+    for key in ("act", "gact", "gW", "gWs", "gb"):
+        for a, b in zip(r1[key], r3[key]):
+            assert np.array_equal(a, b), key
+
+
+def test_call_order_errors():
+    say("case call order")
+    from paper_2605_11517_amd import GnnError
+    cfg, rowptr, colidx = make_config("mini_sage", n=400, m_draw=3000)
+    X, y, m, w = make_inputs(cfg, 400)
+    from paper_2605_11517_amd import Session
+    s = Session(cfg["model"], cfg["dims"], rowptr, colidx, 3, "random", 1, X, w, y, m)
+    c, st = s.ctx, s.stream
+    with pytest.raises(GnnError) as e:
+        c.layer_fwd(1, 0, st)                 # nothing staged
+    assert e.value.status == 4
+    c.gather_boundary(1, 1, st)
+    with pytest.raises(GnnError) as e:
+        c.layer_fwd(1, 0, st)                 # staged for another partition
+    assert e.value.status == 4
+    with pytest.raises(GnnError) as e:
+        c.loss(st)                            # forward incomplete
+    assert e.value.status == 4
+    with pytest.raises(GnnError) as e:
+        c.layer_bwd(3, 1, st)                 # backward before forward + loss
+    assert e.value.status == 4
+    with pytest.raises(GnnError) as e:
+        c.gather_boundary(0, 0, st)
+    assert e.value.status == 1
+    with pytest.raises(GnnError) as e:
+        c.gather_boundary(1, 3, st)
+    assert e.value.status == 1
+    s.epoch()                                 # still usable
+
+
+EDGE = [
+    # (model, dims, n, m_draw, symmetric, k, mode, has_bias)
+    ("gcn", (7, 9, 5), 300, 1500, True, 3, "random", True),        # widths not multiples of 4
+    ("sage", (10, 6, 3), 257, 1200, False, 4, "lp", False),        # no bias, directed, empty rows
+    ("gcn", (64, 32, 8), 500, 4000, True, 1, "random", True),      # k = 1: no boundary at all
+    ("sage", (12, 12, 4), 64, 300, True, 64, "user", True),        # k = n: every vertex alone
+    ("gcn", (132, 260, 70), 700, 9000, True, 5, "lp", True),       # several GEMM tiles + ragged tails
+    ("sage", (1028, 16, 4), 200, 1500, True, 2, "random", True),   # rows wider than 1024 floats
+]
+
+
+@pytest.mark.parametrize("case", EDGE, ids=lambda c: "%s-%s-k%d" % (c[0], "x".join(map(str, c[1])), c[5]))
+def test_edge_shapes(case):
+    model, dims, n, m_draw, sym, k, mode, has_bias = case
+    say("case edge %s" % (case,))
+    rowptr, colidx = small_graph(n, m_draw, seed=31, symmetric=sym, self_loops=False)
+    cfg = dict(model=model, dims=dims, seed=77, train_frac=0.5)
+    X, y, m, w = make_inputs(cfg, n)
+    user = np.arange(n, dtype=np.int32) if mode == "user" else None
+    ref = og.epoch(model, rowptr, colidx, dims, X, w, y, m)
+    s, loss = run_session(cfg, rowptr, colidx, X, y, m, w, k, mode, 5, has_bias=has_bias,
+                          user_part=user)
+    if not has_bias:
+        ref_nb = og.epoch(model, rowptr, colidx, dims, X,
+                          [dict(W=l["W"], Ws=l["Ws"], b=None) for l in w], y, m)
+        ref = ref_nb
+    assert abs(loss - ref["loss"]) <= TOL * abs(ref["loss"])
+    compare(s.results(), ref, model, has_bias=has_bias, tag=str(case))
+
+
+def test_empty_graph_and_empty_partitions():
+    say("case empty graph / empty partitions")
+    n, dims = 40, (8, 8, 4)
+    rowptr, colidx = empty_graph(n)
+    cfg = dict(model="gcn", dims=dims, seed=3, train_frac=0.5)
+    X, y, m, w = make_inputs(cfg, n)
+    part = np.zeros(n, dtype=np.int32)
+    part[5:9] = 2                                  # partition 1 is empty
+    ref = og.epoch("gcn", rowptr, colidx, dims, X, w, y, m)
+    s, loss = run_session(cfg, rowptr, colidx, X, y, m, w, 3, "user", 0, user_part=part)
+    assert abs(loss - ref["loss"]) <= TOL * abs(ref["loss"])
+    compare(s.results(), ref, "gcn", tag="empty")
+    cfg = dict(model="sage", dims=dims, seed=3, train_frac=0.5)
+    X, y, m, w = make_inputs(cfg, n)
+    ref = og.epoch("sage", rowptr, colidx, dims, X, w, y, m)
+    s, loss = run_session(cfg, rowptr, colidx, X, y, m, w, 3, "user", 0, user_part=part)
+    compare(s.results(), ref, "sage", tag="empty-sage")
+
+
+def test_result_does_not_depend_on_k():
+    say("case k-invariance on the GPU")
+    cfg, rowptr, colidx = make_config("mini_gcn_directed")
+    n = cfg["n"]
+    X, y, m, w = make_inputs(cfg, n)
+    base = None
+    for k, mode in [(1, "random"), (2, "lp"), (7, "random"), (50, "lp")]:
+        s, loss = run_session(cfg, rowptr, colidx, X, y, m, w, k, mode, 11)
+        r = s.results()
+        if base is None:
+            base = r
+            continue
+        for key in ("act", "gW", "gb", "gact"):
+            for a, b in zip(r[key], base[key]):
+                assert rel_err(a, b) <= TOL, (key, k)

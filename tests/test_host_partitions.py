@@ -1,0 +1,139 @@
+"""Host logic of the library (no GPU): partition assignment, boundary lists and statistics
+must equal the oracle's set arithmetic bit for bit; argument errors are reported, not fatal;
+the shared library exports every symbol the header declares."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+from helpers import small_graph
+from oracle import partition as op
+from paper_2605_11517_amd import Context, GnnError, load_library
+from synth import make_config
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = load_library()
+    text = open(os.path.join(ROOT, "include", "gnnmi.h")).read()
+    names = set(re.findall(r"\b(gnn_[a-z_]+)\s*\(", text))
+    assert {"gnn_build_partitions", "gnn_gather_boundary", "gnn_layer_fwd", "gnn_layer_bwd",
+            "gnn_epoch"} <= names
+    for name in names:
+        assert hasattr(lib, name), name
+
+
+@pytest.mark.parametrize("name,mode", [("tiny", "random"), ("tiny", "lp"), ("mini_sage", "lp"),
+                                       ("mini_gcn_directed", "lp"), ("mini_gcn_directed", "random")])
+def test_assignment_and_boundaries_match_oracle(name, mode):
+    cfg, rowptr, colidx = make_config(name)
+    n, k, seed = cfg["n"], cfg["k"], cfg["seed"]
+    ctx = Context(cfg["model"], cfg["dims"])
+    ctx.build_partitions(rowptr, colidx, k, mode, seed)
+    part, kk = ctx.get_partition()
+    ref = op.assign_random(n, k, seed) if mode == "random" else op.assign_lp(rowptr, colidx, k, seed)
+    assert kk == k and part.dtype == np.int32
+    assert np.array_equal(part, ref)
+    total = 0
+    for p in range(k):
+        got = ctx.get_boundary(p)
+        want = op.boundary(rowptr, colidx, ref, p)
+        assert np.array_equal(got, want)
+        total += len(want)
+    st = ctx.get_stats()
+    assert st["sum_boundary"] == total and st["n"] == n and st["k"] == k
+    # expansion ratio: required vertices over target vertices
+    alpha = op.alpha(rowptr, colidx, ref, k, self_loops=(cfg["model"] == "gcn"))
+    assert abs(st["sum_required"] / n - alpha) < 1e-12
+    # operator entries: A + I for GCN (one self-loop each), A for SAGE
+    if cfg["model"] == "gcn":
+        has_self = sum(1 for v in range(n) if v in colidx[rowptr[v]:rowptr[v + 1]])
+        assert st["nnz"] == rowptr[-1] + n - has_self
+    else:
+        assert st["nnz"] == rowptr[-1]
+    order, off = ctx.get_order()
+    assert np.array_equal(np.sort(order), np.arange(n))
+    for p in range(k):
+        rows = order[off[p]:off[p + 1]]
+        assert np.all(ref[rows] == p) and np.all(np.diff(rows) > 0)
+
+
+def test_user_assignment_with_empty_and_singleton_partitions():
+    n = 50
+    rowptr, colidx = small_graph(n, 300, seed=3)
+    part = np.zeros(n, dtype=np.int32)
+    part[7] = 2                          # partition 1 is empty, partition 2 holds one vertex
+    ctx = Context("sage", (4, 3))
+    ctx.build_partitions(rowptr, colidx, 3, "user", user_part=part)
+    assert np.array_equal(ctx.get_partition()[0], part)
+    for p in range(3):
+        assert np.array_equal(ctx.get_boundary(p), op.boundary(rowptr, colidx, part, p))
+    assert len(ctx.get_boundary(1)) == 0
+    # k = n: every vertex alone
+    ctx.build_partitions(rowptr, colidx, n, "user", user_part=np.arange(n, dtype=np.int32))
+    for p in (0, 7, n - 1):
+        assert np.array_equal(ctx.get_boundary(p),
+                              op.boundary(rowptr, colidx, np.arange(n), p))
+    # k = 1: nothing crosses
+    ctx.build_partitions(rowptr, colidx, 1, "random", seed=9)
+    assert len(ctx.get_boundary(0)) == 0 and ctx.get_stats()["sum_boundary"] == 0
+
+
+def test_argument_errors_are_reported():
+    rowptr, colidx = small_graph(30, 100, seed=1)
+    with pytest.raises(GnnError) as e:
+        Context("gcn", (4, 0, 3))
+    assert e.value.status == 1
+    with pytest.raises(GnnError) as e:
+        Context("gcn", (4, 3), dtype=7)
+    assert e.value.status == 1
+    ctx = Context("gcn", (4, 3))
+    with pytest.raises(GnnError) as e:
+        ctx.get_stats()
+    assert e.value.status == 4                                   # nothing built yet
+    for k in (0, 31):
+        with pytest.raises(GnnError) as e:
+            ctx.build_partitions(rowptr, colidx, k, "random")
+        assert e.value.status == 1
+    bad = colidx.copy()
+    bad[0], bad[1] = bad[1], bad[0]                              # not ascending
+    if rowptr[1] >= 2:
+        with pytest.raises(GnnError):
+            ctx.build_partitions(rowptr, bad, 2, "random")
+    bad = colidx.copy()
+    bad[-1] = 30                                                 # out of range
+    with pytest.raises(GnnError):
+        ctx.build_partitions(rowptr, bad, 2, "random")
+    rp = rowptr.copy()
+    rp[3] = rp[2] - 1 if rp[2] > 0 else rp[3]
+    if rp[3] < rp[2]:
+        with pytest.raises(GnnError):
+            ctx.build_partitions(rp, colidx, 2, "random")
+    with pytest.raises(GnnError):
+        ctx.build_partitions(rowptr, colidx, 2, "user", user_part=np.full(30, 5, dtype=np.int32))
+    with pytest.raises(GnnError) as e:
+        ctx.build_partitions(rowptr, colidx, 2, "user")           # user_part missing
+    assert e.value.status == 1
+    # a context that failed to build still works afterwards
+    ctx.build_partitions(rowptr, colidx, 2, "random")
+    assert ctx.get_stats()["k"] == 2
+    with pytest.raises(GnnError) as e:
+        ctx.get_boundary(2)
+    assert e.value.status == 1
+    with pytest.raises(GnnError) as e:
+        ctx.gather_boundary(1, 0, None)                           # not bound
+    assert e.value.status == 4
+    with pytest.raises(GnnError) as e:
+        ctx.epoch(None)
+    assert e.value.status == 4
+
+
+def test_unsupported_requests_say_so():
+    with pytest.raises(GnnError) as e:
+        Context("gcn", (4, 3), dtype=1)                           # bf16 storage
+    assert e.value.status == 5
+    with pytest.raises(GnnError) as e:
+        Context("gcn", (4, 3), hbm_budget_bytes=1 << 20)          # streaming schedule
+    assert e.value.status == 5
