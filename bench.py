@@ -61,12 +61,9 @@ def gemm_flops(stats, dims, model):
     return {"gemm_fwd": fwd, "gemm_dw": dw, "gemm_dz": dz}
 
 
-def cpu_baseline(cfg, scale_n, log_fn):
-    """The oracle, as it stands, timed on the host cores on a down-scaled instance of the same
-    workload (same generator, degree and widths; fewer vertices)."""
+def _oracle_epoch_seconds(cfg, n):
     from oracle import fullgraph as og
     from synth import features, glorot_weights, labels_and_mask, rmat_graph
-    n = scale_n
     m_draw = int(cfg["m_draw"] * (n / cfg["n"]))
     rowptr, colidx = rmat_graph(n, m_draw, cfg["seed"] + 1000, symmetric=cfg["symmetric"],
                                 self_loops=cfg["self_loops"])
@@ -78,10 +75,24 @@ def cpu_baseline(cfg, scale_n, log_fn):
     og.epoch(cfg["model"], rowptr, colidx, dims, X, w, y, m)
     dt = time.perf_counter() - t0
     nnz = int(rowptr[-1]) + (n if cfg["model"] == "gcn" and not cfg["self_loops"] else 0)
-    log_fn("cpu oracle: n=%d nnz=%d epoch %.2f s on %d threads" % (n, nnz, dt, og.num_threads()))
+    return dt, nnz
+
+
+def cpu_baseline(cfg, scale_n, log_fn):
+    """The oracle, as it stands, timed on the host cores on a down-scaled instance of the same
+    workload (same generator, degree and widths; fewer vertices).  With scale_n == 0 a short
+    probe run picks the sample size that gives roughly 15 s of CPU work on this machine."""
+    from oracle import fullgraph as og
+    if scale_n <= 0:
+        probe_n = max(2000, min(cfg["n"], 20000))
+        dt, _ = _oracle_epoch_seconds(cfg, probe_n)
+        scale_n = int(max(probe_n, min(cfg["n"], 1_000_000, probe_n * 15.0 / max(dt, 1e-3))))
+        log_fn("cpu oracle probe: n=%d took %.2f s -> sample n=%d" % (probe_n, dt, scale_n))
+    dt, nnz = _oracle_epoch_seconds(cfg, scale_n)
+    log_fn("cpu oracle: n=%d nnz=%d epoch %.2f s on %d threads" % (scale_n, nnz, dt, og.num_threads()))
     return {"value": nnz / dt, "unit": "edges/s", "cores": og.num_threads(), "kind": "oracle",
             "sample": "same R-MAT recipe and layer widths at n=%d (%d operator entries), one fp64 "
-                      "full-graph epoch in %.2f s" % (n, nnz, dt),
+                      "full-graph epoch (fwd+loss+bwd) in %.2f s" % (scale_n, nnz, dt),
             "epoch_s": dt}
 
 
@@ -93,6 +104,9 @@ def main():
     ap.add_argument("--workload", default="mid")
     ap.add_argument("--cpu-sample-n", type=int, default=0, help="vertices of the oracle sample (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device-to-device copy (a dispatch of known "
+                         "size, used to scale hardware byte counters)")
     ap.add_argument("--no-profile", action="store_true",
                     help="leave the per-kernel HIP events out of the timed region")
     args = ap.parse_args()
@@ -122,6 +136,13 @@ def main():
         stats["k"], stats["sum_required"] / n, stats["sum_boundary"], time.perf_counter() - t1))
     del X, rowptr, colidx
 
+    if args.copy_calibration:
+        a = torch.empty(1 << 28, dtype=torch.float32, device="cuda:0").normal_()
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        b.copy_(a)                             # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del a, b
     for _ in range(args.warmup):
         s.epoch()
     torch.cuda.synchronize()
@@ -175,18 +196,39 @@ def main():
         passes = 2 * (len(dims) - 1)
         tp_ms = prof["spmm_t"][0]
         out["aggregated_edges_per_s"] = nnz * (passes + len(dims) - 2) * args.steps / ((sp_ms + tp_ms) * 1e-3)
-        achieved = ab["spmm"] * args.steps / (sp_ms * 1e-3) / 1e9
+        # dominant kernel: k_spmm_items, every launch of it (forward, recompute and transposed)
+        k_ms = sp_ms + tp_ms
+        k_launches = sp_launches + prof["spmm_t"][1]
+        k_bytes = (ab["spmm"] + ab["spmm_t"]) * args.steps
+        achieved = k_bytes / (k_ms * 1e-3) / 1e9
+        # measured HBM-side traffic of the same kernel from the committed counter summary
+        # (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a plain copy), per launch
+        traffic = None
+        from paper_2605_11517_amd.profiling import read_traffic
+        table = read_traffic(os.path.join(ROOT, "profiles", "pmc_%s_epoch.md" % args.workload))
+        if table:
+            rows = [v for k, v in table.items() if k.startswith("k_spmm_items")]
+            if rows:
+                tot_l = sum(r["launches"] for r in rows)
+                traffic = sum(r["bytes_per_launch"] * r["launches"] for r in rows) / tot_l
+        L = len(dims) - 1
+        upper = sum((2 if l == 0 else 3) * (stats["nnz"] * (4 + dims[l] * 4) + n * dims[l] * 4)
+                    for l in range(L))
         out["roofline"] = {
-            "kernel": "k_spmm_wave_row (aggregation, forward + recompute)",
+            "kernel": "k_spmm_items (aggregation over T_p and T_p^T: forward, recompute, transposed)",
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-            "bytes_per_launch": ab["spmm"] * args.steps / sp_launches,
-            "avg_launch_ms": sp_ms / sp_launches, "launches": sp_launches,
+            "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+            "bytes_per_launch": k_bytes / k_launches,
+            "avg_launch_ms": k_ms / k_launches, "launches_per_epoch": k_launches / args.steps,
+            "no_reuse_bytes_per_launch": upper * args.steps / k_launches,
+            "note": "achieved = bytes the method must move if every needed source row is read "
+                    "once per partition, over the HIP-event time of the kernel; traffic = measured "
+                    "fetch+write bytes per launch (rocprofv3 counters); no_reuse = one source row "
+                    "read per operator entry",
         }
         out["profiled_ms_per_step"] = sum(v[0] for v in prof.values()) / args.steps
     if not args.no_cpu_baseline:
-        sample_n = args.cpu_sample_n or max(2000, min(n, 100000))
-        out["cpu_baseline"] = cpu_baseline(cfg, sample_n, log)
+        out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_sample_n, log)
     out["paper_context"] = ("paper reports whole-system epochs only (SSD+PCIe bound): 7.2 s for a "
                             "3-layer GCN on ogbn-products (2.45M nodes / 61.9M edges) on one RTX A5000")
     print(json.dumps(out), flush=True)

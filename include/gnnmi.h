@@ -83,8 +83,9 @@ typedef enum {
     GNN_K_GEMM_DZ = 6,  /* dY W^T (+ dY W_s^T) */
     GNN_K_SPMM_T = 7,   /* transposed aggregation */
     GNN_K_SCATTER = 8,  /* scatter-add onto owners */
-    GNN_K_OTHER = 9,    /* zero fills, reductions */
-    GNN_K_COUNT = 10
+    GNN_K_OTHER = 9,    /* zero fills */
+    GNN_K_SPMM_REDUCE = 10, /* long-row partial sums of both aggregation directions */
+    GNN_K_COUNT = 11
 } gnn_kernel_class;
 
 /* ---- lifetime -------------------------------------------------------------------------- */
@@ -198,7 +199,8 @@ gnn_status gnn_epoch(gnn_ctx *ctx, void *stream, float *loss_out);
 
 /* ---- measurement ------------------------------------------------------------------------ */
 
-/* When enabled, every kernel launch of gnn_epoch is bracketed by HIP events on `stream`;
+/* When enabled, every kernel class of gnn_epoch is bracketed by HIP events on `stream`
+ * (GNN_K_GATHER, GNN_K_SPMM, GNN_K_SPMM_T and GNN_K_SCATTER brackets hold exactly one kernel);
  * after the epoch gnn_get_profile() returns, per kernel class, the summed duration in
  * milliseconds and the launch count of the last epoch.  Adds event overhead; keep it off
  * for wall-clock timing. */

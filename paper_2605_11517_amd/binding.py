@@ -15,7 +15,7 @@ GNN_GCN, GNN_SAGE_MEAN = 0, 1
 GNN_F32, GNN_BF16 = 0, 1
 GNN_PART_USER, GNN_PART_RANDOM, GNN_PART_LP = 0, 1, 2
 KERNEL_CLASSES = ("gather", "spmm", "gemm_fwd", "loss", "act_bwd", "gemm_dw", "gemm_dz",
-                  "spmm_t", "scatter", "other")
+                  "spmm_t", "scatter", "other", "spmm_reduce")
 STATUS = {0: "GNN_OK", 1: "GNN_EINVAL", 2: "GNN_ENOMEM", 3: "GNN_EHIP", 4: "GNN_ESTATE",
           5: "GNN_EUNSUPPORTED"}
 _MODEL = {"gcn": GNN_GCN, "sage": GNN_SAGE_MEAN}

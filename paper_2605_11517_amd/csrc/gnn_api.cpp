@@ -27,11 +27,20 @@ struct DevMeta {
     int32_t* tcol = nullptr;
     float* tw = nullptr;
     int32_t* order = nullptr;
+    struct Plan {
+        int32_t* range_rows = nullptr;
+        int32_t* seg_row = nullptr;
+        int64_t* seg_begin = nullptr;
+        int32_t* seg_len = nullptr;
+        int32_t* long_row = nullptr;
+        int32_t* long_first = nullptr;
+        int32_t* long_nseg = nullptr;
+    } fwd, bwd;
     bool ready = false;
 };
 
 struct Workspace {  // byte offsets into `scratch`
-    int64_t z = 0, dy = 0, dz = 0, dga = 0, partial = 0, colpart = 0, losspart = 0, scalars = 0;
+    int64_t z = 0, dy = 0, dz = 0, dga = 0, partial = 0, colpart = 0, losspart = 0, scalars = 0, segpart = 0;
     int64_t staging_bytes = 0, scratch_bytes = 0;
 };
 
@@ -89,6 +98,15 @@ void free_device(DevMeta& D)
     if (D.tcol) (void)hipFree(D.tcol);
     if (D.tw) (void)hipFree(D.tw);
     if (D.order) (void)hipFree(D.order);
+    for (DevMeta::Plan* P : {&D.fwd, &D.bwd}) {
+        if (P->range_rows) (void)hipFree(P->range_rows);
+        if (P->seg_row) (void)hipFree(P->seg_row);
+        if (P->seg_begin) (void)hipFree(P->seg_begin);
+        if (P->seg_len) (void)hipFree(P->seg_len);
+        if (P->long_row) (void)hipFree(P->long_row);
+        if (P->long_first) (void)hipFree(P->long_first);
+        if (P->long_nseg) (void)hipFree(P->long_nseg);
+    }
     D = DevMeta{};
 }
 
@@ -118,6 +136,17 @@ gnn_status ensure_device(gnn_ctx* c)
     step(upload(D.tcol, M.tcol));
     step(upload(D.tw, M.tw));
     step(upload(D.order, M.order));
+    for (int dir = 0; dir < 2; ++dir) {
+        const HostMeta::Plan& H = dir == 0 ? M.plan_fwd : M.plan_bwd;
+        DevMeta::Plan& P = dir == 0 ? D.fwd : D.bwd;
+        step(upload(P.range_rows, H.range_rows));
+        step(upload(P.seg_row, H.seg_row));
+        step(upload(P.seg_begin, H.seg_begin));
+        step(upload(P.seg_len, H.seg_len));
+        step(upload(P.long_row, H.long_row));
+        step(upload(P.long_first, H.long_first));
+        step(upload(P.long_nseg, H.long_nseg));
+    }
     if (e != hipSuccess) {
         free_device(D);
         (void)hipGetLastError();
@@ -154,6 +183,7 @@ void compute_workspace(gnn_ctx* c)
     w.colpart = take(act_bwd_partial_floats(max_np, (int32_t)dout));
     w.losspart = take(loss_partial_floats(M.n));
     w.scalars = take(64);
+    w.segpart = take(std::max(M.plan_fwd.max_segs, M.plan_bwd.max_segs) * din);
     w.scratch_bytes = o;
 }
 
@@ -215,6 +245,24 @@ gnn_status check_lp(gnn_ctx* c, int32_t layer, int32_t p)
     return GNN_OK;
 }
 
+SpmmItems plan_items(const HostMeta::Plan& H, const DevMeta::Plan& P, int32_t p)
+{
+    SpmmItems it;
+    const int64_t r0 = H.range_off[(size_t)p], s0 = H.seg_off[(size_t)p], l0 = H.long_off[(size_t)p];
+    it.nranges = H.range_off[(size_t)p + 1] - r0 - 1;
+    if (it.nranges < 0) it.nranges = 0;
+    it.range_rows = P.range_rows ? P.range_rows + r0 : nullptr;
+    it.nsegs = H.seg_off[(size_t)p + 1] - s0;
+    it.seg_row = P.seg_row ? P.seg_row + s0 : nullptr;
+    it.seg_begin = P.seg_begin ? P.seg_begin + s0 : nullptr;
+    it.seg_len = P.seg_len ? P.seg_len + s0 : nullptr;
+    it.nlong = H.long_off[(size_t)p + 1] - l0;
+    it.long_row = P.long_row ? P.long_row + l0 : nullptr;
+    it.long_first = P.long_first ? P.long_first + l0 : nullptr;
+    it.long_nseg = P.long_nseg ? P.long_nseg + l0 : nullptr;
+    return it;
+}
+
 // Z_p = S_p [own rows ; staging]
 void run_spmm_fwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
 {
@@ -222,9 +270,19 @@ void run_spmm_fwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
     const int64_t r0 = M.off[(size_t)p], np = M.off[(size_t)p + 1] - r0;
     const int32_t din = c->dims[(size_t)layer - 1];
     const float* in = c->layer_input(layer);
-    launch_spmm(c->D.rp + r0, c->D.lcol, c->D.ew, c->D.rscale ? c->D.rscale + r0 : nullptr,
-                in + r0 * din, np, (const float*)c->staging, (float*)(c->scratch + c->ws.z), np, din,
-                s);
+    const SpmmItems items = plan_items(M.plan_fwd, c->D.fwd, p);
+    const float* rscale = c->D.rscale ? c->D.rscale + r0 : nullptr;
+    float* Z = (float*)(c->scratch + c->ws.z);
+    float* segpart = (float*)(c->scratch + c->ws.segpart);
+    {
+        Timed t(c, s, GNN_K_SPMM);
+        launch_spmm(c->D.rp + r0, c->D.lcol, c->D.ew, rscale, in + r0 * din, np,
+                    (const float*)c->staging, Z, np, din, items, segpart, s);
+    }
+    if (items.nlong > 0) {
+        Timed t(c, s, GNN_K_SPMM_REDUCE);
+        launch_spmm_reduce(rscale, Z, din, items, segpart, s);
+    }
 }
 
 }  // namespace
@@ -435,10 +493,7 @@ gnn_status gnn_layer_fwd(gnn_ctx* c, int32_t layer, int32_t p, void* stream)
     const int32_t din = c->dims[(size_t)layer - 1], dout = c->dims[(size_t)layer];
     const float* in = c->layer_input(layer);
     float* Z = (float*)(c->scratch + c->ws.z);
-    {
-        Timed t(c, s, GNN_K_SPMM);
-        run_spmm_fwd(c, layer, p, s);
-    }
+    run_spmm_fwd(c, layer, p, s);
     {
         Timed t(c, s, GNN_K_GEMM_FWD);
         GemmSeg seg[2];
@@ -536,10 +591,7 @@ gnn_status gnn_layer_bwd(gnn_ctx* c, int32_t layer, int32_t p, void* stream)
         }
     }
     // recompute the aggregate from the regathered rows
-    {
-        Timed t(c, s, GNN_K_SPMM);
-        run_spmm_fwd(c, layer, p, s);
-    }
+    run_spmm_fwd(c, layer, p, s);
     // weight gradients, summed over partitions
     {
         Timed t(c, s, GNN_K_GEMM_DW);
@@ -555,9 +607,18 @@ gnn_status gnn_layer_bwd(gnn_ctx* c, int32_t layer, int32_t p, void* stream)
             launch_gemm_nt(dY, dout, W, dout, dZ, din, np, din, dout, ep, s);
         }
         {
-            Timed t(c, s, GNN_K_SPMM_T);
             const int64_t t0 = M.toff[(size_t)p];
-            launch_spmm(c->D.trp + t0, c->D.tcol, c->D.tw, nullptr, dZ, np, nullptr, dGA, np + nb, din, s);
+            const SpmmItems items = plan_items(M.plan_bwd, c->D.bwd, p);
+            float* segpart = (float*)(c->scratch + c->ws.segpart);
+            {
+                Timed t(c, s, GNN_K_SPMM_T);
+                launch_spmm(c->D.trp + t0, c->D.tcol, c->D.tw, nullptr, dZ, np, nullptr, dGA, np + nb,
+                            din, items, segpart, s);
+            }
+            if (items.nlong > 0) {
+                Timed t(c, s, GNN_K_SPMM_REDUCE);
+                launch_spmm_reduce(nullptr, dGA, din, items, segpart, s);
+            }
         }
         {
             Timed t(c, s, GNN_K_SCATTER);

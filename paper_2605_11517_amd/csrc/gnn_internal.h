@@ -37,7 +37,27 @@ struct HostMeta {
     std::vector<int32_t> tcol;      // local destination row (0 .. n_p)
     std::vector<float> tw;          // weight of the entry (both models)
     gnn_stats stats{};
+    // work decomposition of the aggregation kernels (forward operator and its transpose)
+    struct Plan {
+        std::vector<int64_t> range_off;   // k+1, offsets into range_rows (partition p has
+                                          // range_off[p+1]-range_off[p] boundaries = ranges + 1)
+        std::vector<int32_t> range_rows;  // local row boundaries of consecutive row ranges
+        std::vector<int64_t> seg_off;     // k+1, offsets into the seg_* arrays
+        std::vector<int32_t> seg_row;     // local row a segment belongs to
+        std::vector<int64_t> seg_begin;   // first entry (absolute position)
+        std::vector<int32_t> seg_len;     // entries in the segment
+        std::vector<int64_t> long_off;    // k+1, offsets into long_*
+        std::vector<int32_t> long_row;    // local row split into segments
+        std::vector<int32_t> long_first;  // its first segment (index local to the partition)
+        std::vector<int32_t> long_nseg;   // its number of segments
+        int64_t max_segs = 0;             // most segments in any partition
+    } plan_fwd, plan_bwd;
 };
+
+// Rows with more entries than this are cut into segments of this many entries, each handled
+// by its own wavefront; shorter rows are grouped into ranges of about this many entries.
+constexpr int32_t kSpmmSegment = 512;
+constexpr int32_t kSpmmRangeRows = 64;
 
 // Builds everything above.  Returns GNN_OK or an error with `err` set.
 gnn_status build_host_meta(int model, int64_t n, const int64_t* rowptr, const int32_t* colidx,
@@ -56,10 +76,27 @@ void launch_scatter_rows(const void* src, const int32_t* idx, void* dst, int64_t
 // out[r,:] = rowscale[r] * sum_e w[e] * src(col[e])[:],  e in [rp[r], rp[r+1])
 // src(c) = a_rows + c*d if c < n_a else b_rows + (c - n_a)*d.  w / rowscale may be null (= 1).
 // rp points at the first row's entry of a global row-pointer array; col / w are indexed with
-// the absolute positions stored in rp.
+// the absolute positions stored in rp.  The work is cut into items by a Plan: row ranges
+// (short rows, written directly) and segments of long rows (partial sums into `partial`,
+// one row of d floats per segment, combined in segment order by a second kernel).
+struct SpmmItems {
+    const int32_t* range_rows = nullptr;   // nranges + 1 local row boundaries
+    int64_t nranges = 0;
+    const int32_t* seg_row = nullptr;
+    const int64_t* seg_begin = nullptr;
+    const int32_t* seg_len = nullptr;
+    int64_t nsegs = 0;
+    const int32_t* long_row = nullptr;
+    const int32_t* long_first = nullptr;
+    const int32_t* long_nseg = nullptr;
+    int64_t nlong = 0;
+};
 void launch_spmm(const int64_t* rp, const int32_t* col, const float* w, const float* rowscale,
                  const float* a_rows, int64_t n_a, const float* b_rows, float* out,
-                 int64_t nrows, int32_t d, hipStream_t s);
+                 int64_t nrows, int32_t d, const SpmmItems& items, float* partial, hipStream_t s);
+// second step of the aggregation: combines the segment partial sums of the long rows
+void launch_spmm_reduce(const float* rowscale, float* out, int32_t d, const SpmmItems& items,
+                        float* partial, hipStream_t s);
 
 // dst[map(i),:] += src[i,:] with map(i) = base_row + i for i < n_own, idx[i - n_own] otherwise.
 void launch_scatter_add(const float* src, int64_t nrows, int64_t n_own, int64_t base_row,

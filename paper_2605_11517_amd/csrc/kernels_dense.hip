@@ -7,7 +7,8 @@ namespace {
 
 constexpr int kBlock = 256;
 constexpr int kWave = 64;
-constexpr int kRowsPerBlockAct = 64;
+constexpr int kRowsPerBlockAct = 256;
+constexpr int kLossRowsPerWave = 16;
 
 __device__ inline float wave_max(float v)
 {
@@ -36,9 +37,10 @@ __global__ __launch_bounds__(kBlock) void k_loss(const float* __restrict__ logit
     const unsigned long long cnt = *count;
     const float inv_count = cnt ? 1.f / (float)cnt : 0.f;
     const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
-    const int64_t v = (int64_t)blockIdx.x * (kBlock / kWave) + wave;
     float term = 0.f;
-    if (v < n) {
+    for (int it = 0; it < kLossRowsPerWave; ++it) {
+        const int64_t v = ((int64_t)blockIdx.x * (kBlock / kWave) + wave) * kLossRowsPerWave + it;
+        if (v >= n) break;
         const float* x = logits + v * c;
         float* g = grad + v * c;
         if (mask[v]) {
@@ -50,7 +52,7 @@ __global__ __launch_bounds__(kBlock) void k_loss(const float* __restrict__ logit
             se = wave_sum(se);
             const float lse = mx + logf(se);
             const int32_t y = labels[v];
-            term = lse - x[y];
+            term += lse - x[y];
             for (int j = lane; j < c; j += kWave)
                 g[j] = (expf(x[j] - lse) - (j == y ? 1.f : 0.f)) * inv_count;
         } else {
@@ -128,20 +130,94 @@ __global__ __launch_bounds__(kBlock) void k_act_bwd(const float* __restrict__ g,
     }
 }
 
+// float4 variant for widths that are multiples of 4: cw = d / 4 threads cover one row, the
+// block walks its 256 rows 256 / cw at a time with four row groups in flight, and the row
+// groups are combined through LDS in a fixed order.
+__global__ __launch_bounds__(kBlock) void k_act_bwd_vec(const float* __restrict__ g,
+                                                        const float* __restrict__ act,
+                                                        float* __restrict__ dy, int64_t rows,
+                                                        int32_t d, float* __restrict__ partial)
+{
+    __shared__ float4 sm[kBlock];
+    const int cw = d / 4;
+    const int64_t r0 = (int64_t)blockIdx.x * kRowsPerBlockAct;
+    const int64_t r1 = r0 + kRowsPerBlockAct < rows ? r0 + kRowsPerBlockAct : rows;
+    for (int cc = 0; cc < cw; cc += kBlock) {
+        const int cwe = cw - cc < kBlock ? cw - cc : kBlock;   // float4 columns in this chunk
+        const int rpp = kBlock / cwe;                          // rows per pass
+        const int rsub = threadIdx.x / cwe, cidx = cc + threadIdx.x % cwe;
+        float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (rsub < rpp) {
+            constexpr int U = 4;
+            for (int64_t r = r0 + rsub; r < r1; r += (int64_t)rpp * U) {
+                float4 gv[U], av[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int64_t rr = r + (int64_t)u * rpp;
+                    gv[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                    av[u] = make_float4(1.f, 1.f, 1.f, 1.f);
+                    if (rr < r1) {
+                        gv[u] = reinterpret_cast<const float4*>(g + rr * d)[cidx];
+                        if (act) av[u] = reinterpret_cast<const float4*>(act + rr * d)[cidx];
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int64_t rr = r + (int64_t)u * rpp;
+                    float4 v = gv[u];
+                    v.x = av[u].x > 0.f ? v.x : 0.f;
+                    v.y = av[u].y > 0.f ? v.y : 0.f;
+                    v.z = av[u].z > 0.f ? v.z : 0.f;
+                    v.w = av[u].w > 0.f ? v.w : 0.f;
+                    if (act && rr < r1) reinterpret_cast<float4*>(dy + rr * d)[cidx] = v;
+                    s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+                }
+            }
+        }
+        sm[threadIdx.x] = s;
+        __syncthreads();
+        if (rsub == 0) {
+            for (int q = 1; q < rpp; ++q) {
+                const float4 o = sm[q * cwe + threadIdx.x];
+                s.x += o.x; s.y += o.y; s.z += o.z; s.w += o.w;
+            }
+            reinterpret_cast<float4*>(partial + (int64_t)blockIdx.x * d)[cidx] = s;
+        }
+        __syncthreads();
+    }
+}
+
+// gb[c] += sum_b partial[b, c]: a block owns 32 columns; its 8 row groups walk the partial rows
+// 8 apart and are combined through LDS in a fixed order.
 __global__ __launch_bounds__(kBlock) void k_colsum_finish(const float* __restrict__ partial,
                                                           int64_t nblocks, int32_t d,
                                                           float* __restrict__ gb)
 {
-    const int32_t c = blockIdx.x * kBlock + threadIdx.x;
-    if (c >= d) return;
+    __shared__ float sm[8][32];
+    const int tx = threadIdx.x % 32, ty = threadIdx.x / 32;
+    const int32_t c = blockIdx.x * 32 + tx;
     float s = 0.f;
-    for (int64_t b = 0; b < nblocks; ++b) s += partial[b * d + c];
-    gb[c] += s;
+    if (c < d) {
+        constexpr int U = 4;
+        for (int64_t b = ty; b < nblocks; b += 8 * U) {
+            float x[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) x[u] = b + 8 * u < nblocks ? partial[(b + 8 * u) * d + c] : 0.f;
+#pragma unroll
+            for (int u = 0; u < U; ++u) s += x[u];
+        }
+    }
+    sm[ty][tx] = s;
+    __syncthreads();
+    if (ty == 0 && c < d) {
+        for (int q = 1; q < 8; ++q) s += sm[q][tx];
+        gb[c] += s;
+    }
 }
 
 }  // namespace
 
-int64_t loss_partial_floats(int64_t n) { return (n + 3) / 4 + 1; }
+int64_t loss_partial_floats(int64_t n) { return n / (kLossRowsPerWave * (kBlock / kWave)) + 2; }
 
 void launch_loss(const float* logits, const int32_t* labels, const uint8_t* mask, float* grad,
                  int64_t n, int32_t c, unsigned long long* count_dev, float* partial,
@@ -151,7 +227,8 @@ void launch_loss(const float* logits, const int32_t* labels, const uint8_t* mask
     int64_t cb = (n + kBlock * 64 - 1) / (kBlock * 64);
     hipLaunchKernelGGL(k_count_mask, dim3((unsigned)(cb < 1 ? 1 : cb)), dim3(kBlock), 0, s, mask, n,
                        count_dev);
-    const int64_t blocks = (n + (kBlock / kWave) - 1) / (kBlock / kWave);
+    const int64_t rpb = kLossRowsPerWave * (kBlock / kWave);
+    const int64_t blocks = (n + rpb - 1) / rpb;
     hipLaunchKernelGGL(k_loss, dim3((unsigned)blocks), dim3(kBlock), 0, s, logits, labels, mask,
                        grad, n, c, (const unsigned long long*)count_dev, partial);
     hipLaunchKernelGGL(k_loss_finish, dim3(1), dim3(kBlock), 0, s, (const float*)partial, blocks,
@@ -169,10 +246,17 @@ void launch_act_bwd(const float* g, const float* act, float* dy, int64_t rows, i
     if (rows <= 0) return;
     const int64_t blocks = (rows + kRowsPerBlockAct - 1) / kRowsPerBlockAct;
     if (!act && !gb) return;
-    hipLaunchKernelGGL(k_act_bwd, dim3((unsigned)blocks), dim3(kBlock), 0, s, g, act, dy, rows, d,
-                       partial);
+    const bool vec = d % 4 == 0 && ((reinterpret_cast<uintptr_t>(g) | reinterpret_cast<uintptr_t>(act) |
+                                     reinterpret_cast<uintptr_t>(dy) |
+                                     reinterpret_cast<uintptr_t>(partial)) & 15) == 0;
+    if (vec)
+        hipLaunchKernelGGL(k_act_bwd_vec, dim3((unsigned)blocks), dim3(kBlock), 0, s, g, act, dy, rows,
+                           d, partial);
+    else
+        hipLaunchKernelGGL(k_act_bwd, dim3((unsigned)blocks), dim3(kBlock), 0, s, g, act, dy, rows, d,
+                           partial);
     if (gb)
-        hipLaunchKernelGGL(k_colsum_finish, dim3((unsigned)((d + kBlock - 1) / kBlock)), dim3(kBlock),
+        hipLaunchKernelGGL(k_colsum_finish, dim3((unsigned)((d + 31) / 32)), dim3(kBlock),
                            0, s, (const float*)partial, blocks, d, gb);
 }
 

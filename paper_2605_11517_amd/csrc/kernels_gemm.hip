@@ -220,19 +220,40 @@ __global__ __launch_bounds__(kThreads) void k_gemm(const GemmArgs g)
         }
 }
 
-// c[i] += sum_s partial[s * stride + i], s ascending
+// c[i] += sum_s partial[s * stride + i], s ascending; four consecutive elements per thread,
+// eight splits in flight.
 __global__ __launch_bounds__(256) void k_reduce_partials(const float* __restrict__ partial,
                                                          int32_t splits, int64_t stride,
                                                          float* __restrict__ c, int64_t ldc,
                                                          int32_t m, int32_t n)
 {
+    constexpr int U = 8;
     const int64_t total = (int64_t)m * n;
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total;
-         i += (int64_t)gridDim.x * 256) {
-        float s = 0.f;
-        for (int32_t z = 0; z < splits; ++z) s += partial[(int64_t)z * stride + i];
-        const int64_t r = i / n, cc = i - r * n;
-        c[r * ldc + cc] += s;
+    const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (i >= total) return;
+    const bool full = (i + 3 < total) && (stride % 4 == 0);
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    if (full) {
+        for (int32_t z0 = 0; z0 < splits; z0 += U) {
+            float4 x[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                x[u] = z0 + u < splits
+                           ? *reinterpret_cast<const float4*>(partial + (int64_t)(z0 + u) * stride + i)
+                           : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+            for (int u = 0; u < U; ++u) { acc[0] += x[u].x; acc[1] += x[u].y; acc[2] += x[u].z; acc[3] += x[u].w; }
+        }
+    } else {
+        for (int32_t z = 0; z < splits; ++z)
+            for (int e = 0; e < 4; ++e)
+                if (i + e < total) acc[e] += partial[(int64_t)z * stride + i + e];
+    }
+    for (int e = 0; e < 4; ++e) {
+        const int64_t j = i + e;
+        if (j >= total) break;
+        const int64_t r = j / n, cc = j - r * n;
+        c[r * ldc + cc] += acc[e];
     }
 }
 
@@ -311,7 +332,7 @@ void launch_gemm_nt(const float* a, int64_t lda, const float* b, int64_t ldb, fl
 int gemm_tn_splits(int64_t kdim, int32_t m, int32_t n)
 {
     const int64_t tiles = (int64_t)((m + 127) / 128) * ((n + 127) / 128);
-    int64_t want = (1024 + tiles - 1) / tiles;          // ~4 workgroups per CU
+    int64_t want = (512 + tiles - 1) / tiles;           // ~2 workgroups per CU
     int64_t most = (kdim + 16 * BK - 1) / (16 * BK);    // at least 16 k-steps per split
     int64_t sp = want < most ? want : most;
     return (int)(sp < 1 ? 1 : sp);
@@ -333,8 +354,8 @@ void launch_gemm_tn(const float* a, int64_t lda, const float* b, int64_t ldb, fl
     g.split_chunk = chunk;
     g.split_stride = (int64_t)m * n;
     launch_gemm<false, false>(g, splits, s);
-    int64_t blocks = ((int64_t)m * n + 255) / 256;
-    hipLaunchKernelGGL(k_reduce_partials, dim3((unsigned)(blocks > 1024 ? 1024 : blocks)), dim3(256),
+    int64_t blocks = ((int64_t)m * n + 1023) / 1024;
+    hipLaunchKernelGGL(k_reduce_partials, dim3((unsigned)blocks), dim3(256),
                        0, s, (const float*)partial, splits, (int64_t)m * n, c, ldc, m, n);
 }
 

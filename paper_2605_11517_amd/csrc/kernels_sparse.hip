@@ -81,77 +81,98 @@ void move_rows(const void* src, const int32_t* idx, void* dst, int64_t rows, int
 }
 
 // ---------------------------------------------------------------------------------------------
-// CSR aggregation, one wavefront per output row.
+// CSR aggregation, one wavefront per work item.
 //
-// The 64 lanes are split into S = 64 / G slots of G lanes.  A slot owns one entry of the row
+// Work items come from a host-built plan so that every wavefront sees about the same number of
+// entries whatever the degree distribution: an item is either a range of consecutive short
+// rows (results written directly) or one segment of a long row (partial sum written to
+// `partial`, combined afterwards in segment order, which keeps the result deterministic).
+//
+// Inside a row the 64 lanes are split into S = 64 / G slots of G lanes.  A slot owns one entry
 // at a time and its lanes read that source row as float4 (16 B per lane, a full row of
 // d <= 4 G floats per slot in one coalesced request); NV > 1 covers wider rows.  The wave
-// first loads 64 column indices and weights with one coalesced read each, then hands them to
-// the slots with cross-lane reads, so the index stream costs 8 B per entry and the feature
-// rows dominate.  Slot partial sums are combined with xor-shuffles at the end of the row.
+// loads 64 column indices and weights with one coalesced read each and hands them to the slots
+// with cross-lane reads, so the index stream costs 4-8 B per entry and the feature rows
+// dominate.  Slot partial sums are combined with xor-shuffles at the end of the row.
 // ---------------------------------------------------------------------------------------------
+struct SpmmArgs {
+    const int64_t* rp;
+    const int32_t* col;
+    const float* w;
+    const float* rowscale;
+    const float* a_rows;
+    int64_t n_a;
+    const float* b_rows;
+    float* out;
+    int32_t d, ld;          // d: columns handled by this launch; ld: row stride
+    SpmmItems it;
+    float* partial;
+};
+
 template <int G, int NV, bool VEC>
-__global__ __launch_bounds__(kBlock) void k_spmm_wave_row(
-    const int64_t* __restrict__ rp, const int32_t* __restrict__ col, const float* __restrict__ w,
-    const float* __restrict__ rowscale, const float* __restrict__ a_rows, int64_t n_a,
-    const float* __restrict__ b_rows, float* __restrict__ out, int64_t nrows, int32_t d,
-    int32_t ld)
+__device__ inline void spmm_accumulate(const SpmmArgs& g, int64_t e_begin, int64_t e_end, int lane,
+                                       float (&acc)[NV][4])
 {
     constexpr int S = kWave / G;
-    constexpr int UNROLL = 4;
-    const int lane = threadIdx.x % kWave;
+    constexpr int UNROLL = (NV == 1) ? 8 : 4;   // source rows in flight per slot
     const int slot = lane / G;
     const int gl = lane % G;
-    const int64_t row = (int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;
-    if (row >= nrows) return;
-
-    const int64_t e_begin = rp[row], e_end = rp[row + 1];
-    float acc[NV][4];
+    // column offsets of this lane's float4s; lanes past the row end read column 0 (their sums
+    // are never stored), so that every load below is unconditional and the compiler can keep
+    // all of them in flight
+    int c4[NV];
 #pragma unroll
-    for (int v = 0; v < NV; ++v)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) acc[v][i] = 0.f;
-
+    for (int v = 0; v < NV; ++v) {
+        const int c = (v * G + gl) * 4;
+        c4[v] = c < g.d ? c : 0;
+    }
+    // index/weight chunk of the first 64 entries; the next chunk is fetched while this one is
+    // being consumed
+    int32_t my_c = 0;
+    float my_w = 0.f;
+    if (e_begin + lane < e_end) {
+        my_c = g.col[e_begin + lane];
+        my_w = g.w ? g.w[e_begin + lane] : 1.f;
+    }
     for (int64_t e0 = e_begin; e0 < e_end; e0 += kWave) {
         const int cnt = (int)((e_end - e0) < kWave ? (e_end - e0) : kWave);
-        int32_t my_c = 0;
-        float my_w = 0.f;
-        if (lane < cnt) {
-            my_c = col[e0 + lane];
-            my_w = w ? w[e0 + lane] : 1.f;
+        const int32_t cur_c = my_c;
+        const float cur_w = my_w;
+        if (e0 + kWave + lane < e_end) {
+            my_c = g.col[e0 + kWave + lane];
+            my_w = g.w ? g.w[e0 + kWave + lane] : 1.f;
         }
         for (int j0 = 0; j0 < cnt; j0 += S * UNROLL) {
             const float* src[UNROLL];
             float ww[UNROLL];
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
-                int j = j0 + u * S + slot;
-                int jj = j < cnt ? j : 0;
-                int32_t c = __shfl(my_c, jj, kWave);
-                float wt = __shfl(my_w, jj, kWave);
+                const int j = j0 + u * S + slot;
+                const int jj = j < cnt ? j : cnt - 1;     // stay on a valid entry
+                const int32_t c = __shfl(cur_c, jj, kWave);
+                const float wt = __shfl(cur_w, jj, kWave);
                 ww[u] = j < cnt ? wt : 0.f;
-                src[u] = (c < n_a) ? a_rows + (int64_t)c * ld : b_rows + ((int64_t)c - n_a) * ld;
+                src[u] = (c < g.n_a) ? g.a_rows + (int64_t)c * g.ld
+                                     : g.b_rows + ((int64_t)c - g.n_a) * g.ld;
             }
             if (VEC) {
                 float4 x[UNROLL][NV];
 #pragma unroll
                 for (int u = 0; u < UNROLL; ++u)
 #pragma unroll
-                    for (int v = 0; v < NV; ++v) {
-                        int c4 = (v * G + gl) * 4;
-                        x[u][v] = (c4 < d && ww[u] != 0.f)
-                                      ? *reinterpret_cast<const float4*>(src[u] + c4)
-                                      : make_float4(0.f, 0.f, 0.f, 0.f);
-                    }
+                    for (int v = 0; v < NV; ++v)
+                        x[u][v] = *reinterpret_cast<const float4*>(src[u] + c4[v]);
 #pragma unroll
-                for (int u = 0; u < UNROLL; ++u)
+                for (int u = 0; u < UNROLL; ++u) {
+                    const bool on = (j0 + u * S + slot) < cnt;
 #pragma unroll
                     for (int v = 0; v < NV; ++v) {
-                        acc[v][0] += ww[u] * x[u][v].x;
-                        acc[v][1] += ww[u] * x[u][v].y;
-                        acc[v][2] += ww[u] * x[u][v].z;
-                        acc[v][3] += ww[u] * x[u][v].w;
+                        acc[v][0] += on ? ww[u] * x[u][v].x : 0.f;
+                        acc[v][1] += on ? ww[u] * x[u][v].y : 0.f;
+                        acc[v][2] += on ? ww[u] * x[u][v].z : 0.f;
+                        acc[v][3] += on ? ww[u] * x[u][v].w : 0.f;
                     }
+                }
             } else {
 #pragma unroll
                 for (int u = 0; u < UNROLL; ++u)
@@ -160,7 +181,7 @@ __global__ __launch_bounds__(kBlock) void k_spmm_wave_row(
 #pragma unroll
                         for (int i = 0; i < 4; ++i) {
                             int c = (v * G + gl) * 4 + i;
-                            if (c < d && ww[u] != 0.f) acc[v][i] += ww[u] * src[u][c];
+                            if (c < g.d && ww[u] != 0.f) acc[v][i] += ww[u] * src[u][c];
                         }
             }
         }
@@ -172,21 +193,101 @@ __global__ __launch_bounds__(kBlock) void k_spmm_wave_row(
         for (int v = 0; v < NV; ++v)
 #pragma unroll
             for (int i = 0; i < 4; ++i) acc[v][i] += __shfl_xor(acc[v][i], m, kWave);
-    if (slot == 0) {
-        const float sc = rowscale ? rowscale[row] : 1.f;
-        float* o = out + row * (int64_t)ld;
+}
+
+template <int G, int NV, bool VEC>
+__device__ inline void spmm_store(float* o, int32_t d, int lane, float sc, const float (&acc)[NV][4])
+{
+    if (lane >= G) return;
 #pragma unroll
-        for (int v = 0; v < NV; ++v) {
-            int c4 = (v * G + gl) * 4;
-            if (VEC) {
-                if (c4 < d)
-                    *reinterpret_cast<float4*>(o + c4) =
-                        make_float4(sc * acc[v][0], sc * acc[v][1], sc * acc[v][2], sc * acc[v][3]);
-            } else {
+    for (int v = 0; v < NV; ++v) {
+        int c4 = (v * G + lane) * 4;
+        if (VEC) {
+            if (c4 < d)
+                *reinterpret_cast<float4*>(o + c4) =
+                    make_float4(sc * acc[v][0], sc * acc[v][1], sc * acc[v][2], sc * acc[v][3]);
+        } else {
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    if (c4 + i < d) o[c4 + i] = sc * acc[v][i];
-            }
+            for (int i = 0; i < 4; ++i)
+                if (c4 + i < d) o[c4 + i] = sc * acc[v][i];
+        }
+    }
+}
+
+template <int G, int NV, bool VEC>
+__global__ __launch_bounds__(kBlock) void k_spmm_items(const SpmmArgs g)
+{
+    const int lane = threadIdx.x % kWave;
+    // the item index is the same for the whole wavefront; tell the compiler so that row
+    // pointers and item descriptors travel through scalar registers
+    const int64_t item = __builtin_amdgcn_readfirstlane(
+        (int)(blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave));
+    float acc[NV][4];
+    if (item < g.it.nsegs) {
+        // one segment of a long row -> partial sum
+#pragma unroll
+        for (int v = 0; v < NV; ++v)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc[v][i] = 0.f;
+        const int64_t e0 = g.it.seg_begin[item];
+        spmm_accumulate<G, NV, VEC>(g, e0, e0 + g.it.seg_len[item], lane, acc);
+        spmm_store<G, NV, VEC>(g.partial + item * (int64_t)g.ld, g.d, lane, 1.f, acc);
+        return;
+    }
+    const int64_t ri = item - g.it.nsegs;
+    if (ri >= g.it.nranges) return;
+    const int32_t r_end = g.it.range_rows[ri + 1];
+    for (int32_t row = g.it.range_rows[ri]; row < r_end; ++row) {
+        const int64_t e_begin = g.rp[row], e_end = g.rp[row + 1];
+        if (e_end - e_begin > kSpmmSegment) continue;  // long row: handled by its segments
+#pragma unroll
+        for (int v = 0; v < NV; ++v)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc[v][i] = 0.f;
+        spmm_accumulate<G, NV, VEC>(g, e_begin, e_end, lane, acc);
+        spmm_store<G, NV, VEC>(g.out + row * (int64_t)g.ld, g.d, lane,
+                               g.rowscale ? g.rowscale[row] : 1.f, acc);
+    }
+}
+
+// out[row,:] = rowscale[row] * (partial[first,:] + partial[first+1,:] + ...): one wavefront per
+// long row and 256-float column block, segments added in ascending order (eight loads in
+// flight per lane).
+template <bool VEC>
+__global__ __launch_bounds__(kBlock) void k_spmm_long_reduce(const SpmmArgs g, int32_t c0,
+                                                             int32_t dc)
+{
+    constexpr int U = 8;
+    const int lane = threadIdx.x % kWave;
+    const int64_t i = (int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;
+    if (i >= g.it.nlong) return;
+    const int32_t row = g.it.long_row[i];
+    const int64_t first = g.it.long_first[i];
+    const int32_t ns = g.it.long_nseg[i];
+    const float sc = g.rowscale ? g.rowscale[row] : 1.f;
+    const int32_t cb = c0 + blockIdx.y * 256;          // first column of this block
+    const int32_t cend = c0 + dc;
+    if (VEC) {
+        const int32_t c = cb + lane * 4;
+        if (c >= cend) return;
+        float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int32_t t0 = 0; t0 < ns; t0 += U) {
+            float4 x[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                x[u] = t0 + u < ns
+                           ? *reinterpret_cast<const float4*>(g.partial + (first + t0 + u) * (int64_t)g.ld + c)
+                           : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+            for (int u = 0; u < U; ++u) { s.x += x[u].x; s.y += x[u].y; s.z += x[u].z; s.w += x[u].w; }
+        }
+        *reinterpret_cast<float4*>(g.out + row * (int64_t)g.ld + c) =
+            make_float4(sc * s.x, sc * s.y, sc * s.z, sc * s.w);
+    } else {
+        for (int32_t c = cb + lane; c < cend && c < cb + 256; c += kWave) {
+            float s = 0.f;
+            for (int32_t t = 0; t < ns; ++t) s += g.partial[(first + t) * (int64_t)g.ld + c];
+            g.out[row * (int64_t)g.ld + c] = sc * s;
         }
     }
 }
@@ -240,24 +341,38 @@ void launch_scatter_rows(const void* src, const int32_t* idx, void* dst, int64_t
     move_rows<true>(src, idx, dst, rows, row_bytes, s);
 }
 
+namespace {
+SpmmArgs spmm_args(const int64_t* rp, const int32_t* col, const float* w, const float* rowscale,
+                   const float* a_rows, int64_t n_a, const float* b_rows, float* out, int32_t c0,
+                   int32_t dc, int32_t d, const SpmmItems& items, float* partial)
+{
+    SpmmArgs g;
+    g.rp = rp; g.col = col; g.w = w; g.rowscale = rowscale;
+    g.a_rows = a_rows + c0; g.n_a = n_a; g.b_rows = b_rows ? b_rows + c0 : nullptr;
+    g.out = out + c0; g.d = dc; g.ld = d; g.it = items; g.partial = partial + c0;
+    return g;
+}
+}  // namespace
+
 void launch_spmm(const int64_t* rp, const int32_t* col, const float* w, const float* rowscale,
                  const float* a_rows, int64_t n_a, const float* b_rows, float* out,
-                 int64_t nrows, int32_t d, hipStream_t s)
+                 int64_t nrows, int32_t d, const SpmmItems& items, float* partial, hipStream_t s)
 {
     if (nrows <= 0 || d <= 0) return;
-    const dim3 grid((unsigned)((nrows + (kBlock / kWave) - 1) / (kBlock / kWave)));
+    const int64_t nitems = items.nsegs + items.nranges;
+    if (nitems <= 0) return;
+    const int wpb = kBlock / kWave;
+    const dim3 grid((unsigned)((nitems + wpb - 1) / wpb));
     const dim3 block(kBlock);
     const bool vec = (d % 4 == 0);
-    // rows wider than 1024 floats are processed in column blocks of 1024
+    // rows wider than 1024 floats are processed in column blocks of 1024, one launch each
     for (int32_t c0 = 0; c0 < d; c0 += 1024) {
         const int32_t dc = d - c0 < 1024 ? d - c0 : 1024;
-        const float* a = a_rows + c0;
-        const float* b = b_rows ? b_rows + c0 : nullptr;
-        float* o = out + c0;
+        const SpmmArgs g = spmm_args(rp, col, w, rowscale, a_rows, n_a, b_rows, out, c0, dc, d, items,
+                                     partial);
         const int nv4 = (dc + 3) / 4;  // float4 columns of this block
-#define GNN_SPMM(G, NV, VEC)                                                                   \
-    hipLaunchKernelGGL((k_spmm_wave_row<G, NV, VEC>), grid, block, 0, s, rp, col, w, rowscale, \
-                       a, n_a, b, o, nrows, dc, d)
+#define GNN_SPMM(G, NV, VEC) \
+    hipLaunchKernelGGL((k_spmm_items<G, NV, VEC>), grid, block, 0, s, g)
         if (vec) {
             if (nv4 <= 8) GNN_SPMM(8, 1, true);
             else if (nv4 <= 16) GNN_SPMM(16, 1, true);
@@ -275,6 +390,19 @@ void launch_spmm(const int64_t* rp, const int32_t* col, const float* w, const fl
         }
 #undef GNN_SPMM
     }
+}
+
+void launch_spmm_reduce(const float* rowscale, float* out, int32_t d, const SpmmItems& items,
+                        float* partial, hipStream_t s)
+{
+    if (items.nlong <= 0 || d <= 0) return;
+    const int wpb = kBlock / kWave;
+    const bool vec = (d % 4 == 0);
+    SpmmArgs g = spmm_args(nullptr, nullptr, nullptr, rowscale, nullptr, 0, nullptr, out, 0, d, d, items,
+                           partial);
+    const dim3 rgrid((unsigned)((items.nlong + wpb - 1) / wpb), (unsigned)((d + 255) / 256));
+    if (vec) hipLaunchKernelGGL(k_spmm_long_reduce<true>, rgrid, dim3(kBlock), 0, s, g, 0, d);
+    else hipLaunchKernelGGL(k_spmm_long_reduce<false>, rgrid, dim3(kBlock), 0, s, g, 0, d);
 }
 
 void launch_scatter_add(const float* src, int64_t nrows, int64_t n_own, int64_t base_row,

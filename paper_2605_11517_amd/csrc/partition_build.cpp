@@ -137,6 +137,66 @@ void lp_round(int64_t n, const int64_t* rowptr, const int32_t* colidx, int32_t k
     }
 }
 
+// Cuts the rows [0, nrows) of one partition (row pointers rp[0..nrows], absolute positions)
+// into work items: rows longer than kSpmmSegment become segments of that many entries; the
+// others are grouped into consecutive ranges holding at most kSpmmSegment entries and
+// kSpmmRangeRows rows (a long row closes the range before it and is skipped by range items).
+struct PlanPart {
+    std::vector<int32_t> range_rows, seg_row, seg_len, long_row, long_first, long_nseg;
+    std::vector<int64_t> seg_begin;
+};
+void plan_partition(const int64_t* rp, int64_t nrows, PlanPart& P)
+{
+    P.range_rows.push_back(0);
+    int64_t acc = 0;
+    int32_t start = 0;
+    for (int64_t r = 0; r < nrows; ++r) {
+        const int64_t deg = rp[r + 1] - rp[r];
+        if (deg > kSpmmSegment) {
+            P.long_row.push_back((int32_t)r);
+            P.long_first.push_back((int32_t)P.seg_row.size());
+            int32_t ns = 0;
+            for (int64_t e = rp[r]; e < rp[r + 1]; e += kSpmmSegment) {
+                P.seg_row.push_back((int32_t)r);
+                P.seg_begin.push_back(e);
+                P.seg_len.push_back((int32_t)std::min<int64_t>(kSpmmSegment, rp[r + 1] - e));
+                ++ns;
+            }
+            P.long_nseg.push_back(ns);
+            continue;  // costs a range nothing
+        }
+        if (r > start && (acc + deg > kSpmmSegment || r - start >= kSpmmRangeRows)) {
+            P.range_rows.push_back((int32_t)r);
+            start = (int32_t)r;
+            acc = 0;
+        }
+        acc += deg;
+    }
+    if (nrows > start) P.range_rows.push_back((int32_t)nrows);
+}
+
+void append_plan(HostMeta::Plan& G, int32_t k, std::vector<PlanPart>& parts)
+{
+    G.range_off.assign((size_t)k + 1, 0);
+    G.seg_off.assign((size_t)k + 1, 0);
+    G.long_off.assign((size_t)k + 1, 0);
+    for (int32_t p = 0; p < k; ++p) {
+        PlanPart& P = parts[(size_t)p];
+        G.range_off[(size_t)p + 1] = G.range_off[(size_t)p] + (int64_t)P.range_rows.size();
+        G.seg_off[(size_t)p + 1] = G.seg_off[(size_t)p] + (int64_t)P.seg_row.size();
+        G.long_off[(size_t)p + 1] = G.long_off[(size_t)p] + (int64_t)P.long_row.size();
+        G.max_segs = std::max<int64_t>(G.max_segs, (int64_t)P.seg_row.size());
+        G.range_rows.insert(G.range_rows.end(), P.range_rows.begin(), P.range_rows.end());
+        G.seg_row.insert(G.seg_row.end(), P.seg_row.begin(), P.seg_row.end());
+        G.seg_begin.insert(G.seg_begin.end(), P.seg_begin.begin(), P.seg_begin.end());
+        G.seg_len.insert(G.seg_len.end(), P.seg_len.begin(), P.seg_len.end());
+        G.long_row.insert(G.long_row.end(), P.long_row.begin(), P.long_row.end());
+        G.long_first.insert(G.long_first.end(), P.long_first.begin(), P.long_first.end());
+        G.long_nseg.insert(G.long_nseg.end(), P.long_nseg.begin(), P.long_nseg.end());
+        P = PlanPart{};
+    }
+}
+
 }  // namespace
 
 gnn_status build_host_meta(int model, int64_t n, const int64_t* rowptr, const int32_t* colidx,
@@ -335,6 +395,19 @@ gnn_status build_host_meta(int model, int64_t n, const int64_t* rowptr, const in
                 }
             }
         });
+
+        // ---- phase D: work items of the aggregation kernels -------------------------------------
+        {
+            std::vector<PlanPart> fw((size_t)k), bw((size_t)k);
+            parallel_for(k, 1, [&](int, int64_t p) {
+                const int64_t r0 = M.off[(size_t)p], np = M.off[(size_t)p + 1] - r0;
+                plan_partition(M.rp.data() + r0, np, fw[(size_t)p]);
+                const int64_t t0 = M.toff[(size_t)p], nR = M.toff[(size_t)p + 1] - t0;
+                plan_partition(M.trp.data() + t0, nR, bw[(size_t)p]);
+            });
+            append_plan(M.plan_fwd, k, fw);
+            append_plan(M.plan_bwd, k, bw);
+        }
 
         // ---- stats ---------------------------------------------------------------------------
         gnn_stats& S = M.stats;
