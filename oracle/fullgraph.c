@@ -255,7 +255,7 @@ double oracle_loss(int64_t n, int64_t C, const double *logits, const int32_t *la
 }
 
 /*
- * One full-graph epoch: forward through L layers, loss, and (if do_backward) backward.
+ * Forward through L layers.
  *
  * dims[0..L]           layer widths d_0 .. d_L
  * X        [n, d_0]    input features A^0
@@ -263,42 +263,25 @@ double oracle_loss(int64_t n, int64_t C, const double *logits, const int32_t *la
  * Ws[l]    [d_l, d_{l+1}]   SAGE self weight (ignored for GCN; may be NULL)
  * b[l]     [d_{l+1}]        bias (may be NULL = no bias)
  * act[l]   [n, d_{l+1}]     out: A^{l+1}
- * zagg[l]  [n, d_l]         out (optional, may be NULL array or NULL entries): Z of layer l+1
- * gW, gWs, gb               out: gradients, same shapes as W, Ws, b (NULL entries skipped)
- * gact[l]  [n, d_{l+1}]     out: dLoss/dA^{l+1}  (NULL array or NULL entries skipped)
- * gX       [n, d_0]         out (optional): dLoss/dA^0.  The training pass does not need it
- *                           (the backward loop of the overall-procedure algorithm stops at
- *                           layer 2); tests ask for it so that finite differences on the
- *                           inputs can check the whole backward chain.
+ * zagg[l]  [n, d_l]         out: aggregated input Z of layer l+1
  * Returns 0, or -1 when memory runs out.
  */
-int oracle_epoch(int model, int64_t n, const int64_t *rowptr, const int32_t *colidx, int L,
-                 const int32_t *dims, const double *X, const double *const *W,
-                 const double *const *Ws, const double *const *b, const int32_t *labels,
-                 const uint8_t *mask, double *const *act, double *const *zagg, double *loss,
-                 int do_backward, double *const *gW, double *const *gWs, double *const *gb,
-                 double *const *gact, double *gX)
+int oracle_forward(int model, int64_t n, const int64_t *rowptr, const int32_t *colidx, int L,
+                   const int32_t *dims, const double *X, const double *const *W,
+                   const double *const *Ws, const double *const *b, double *const *act,
+                   double *const *zagg)
 {
     agg_op op;
-    int rc = -1;
-    double **Z = NULL, *G = NULL, *dY = NULL, *dZ = NULL, *Gprev = NULL;
-    int64_t dmax = 0;
-    for (int l = 0; l <= L; ++l)
-        if (dims[l] > dmax) dmax = dims[l];
-    if (agg_build(model, n, rowptr, colidx, &op)) goto done;
-    Z = (double **)calloc((size_t)L, sizeof(double *));
-    if (!Z) goto done;
-
-    /* ---- forward ---- */
+    if (agg_build(model, n, rowptr, colidx, &op)) {
+        agg_free(&op);
+        return -1;
+    }
     for (int l = 0; l < L; ++l) {
         int64_t din = dims[l], dout = dims[l + 1];
         const double *Ain = l == 0 ? X : act[l - 1];
-        Z[l] = (double *)malloc((size_t)(n * din > 0 ? n * din : 1) * sizeof(double));
-        if (!Z[l]) goto done;
-        agg_apply(&op, din, Ain, Z[l]);
-        if (zagg && zagg[l]) memcpy(zagg[l], Z[l], (size_t)(n * din) * sizeof(double));
+        agg_apply(&op, din, Ain, zagg[l]);
         double *Y = act[l];
-        matmul_nn(n, din, dout, Z[l], W[l], Y, 0);
+        matmul_nn(n, din, dout, zagg[l], W[l], Y, 0);
         if (model == ORACLE_SAGE) matmul_nn(n, din, dout, Ain, Ws[l], Y, 1);
 #pragma omp parallel for schedule(static)
         for (int64_t v = 0; v < n; ++v)
@@ -308,38 +291,68 @@ int oracle_epoch(int model, int64_t n, const int64_t *rowptr, const int32_t *col
                 Y[v * dout + c] = y;
             }
     }
+    agg_free(&op);
+    return 0;
+}
 
-    /* ---- loss ---- */
+/*
+ * Loss and backward, given the forward results.
+ *
+ * act, zagg            as returned by oracle_forward
+ * relu_on[l] [n, d_{l+1}]   optional (NULL array or NULL entries): the activation decision of
+ *                      hidden layer l+1 as 0/1 bytes.  By default the decision is act > 0.  A
+ *                      test that compares against an fp32 implementation passes the other
+ *                      side's decision for the few elements whose pre-activation lies within
+ *                      rounding distance of zero, where either choice is a correct result.
+ * gW, gWs, gb          out: gradients, same shapes as W, Ws, b (NULL entries skipped)
+ * gact[l]  [n, d_{l+1}]     out: dLoss/dA^{l+1}  (NULL array or NULL entries skipped)
+ * gX       [n, d_0]         out (optional): dLoss/dA^0.  The training pass does not need it
+ *                           (the backward loop of the overall-procedure algorithm stops at
+ *                           layer 2); tests ask for it so that finite differences on the
+ *                           inputs can check the whole backward chain.
+ * Returns 0, or -1 when memory runs out.
+ */
+int oracle_backward(int model, int64_t n, const int64_t *rowptr, const int32_t *colidx, int L,
+                    const int32_t *dims, const double *X, const double *const *W,
+                    const double *const *Ws, const double *const *act, const double *const *zagg,
+                    const int32_t *labels, const uint8_t *mask, const uint8_t *const *relu_on,
+                    double *loss, double *const *gW, double *const *gWs, double *const *gb,
+                    double *const *gact, double *gX)
+{
+    agg_op op;
+    int rc = -1;
+    double *G = NULL, *dY = NULL, *dZ = NULL, *Gprev = NULL;
+    int64_t dmax = 0;
+    for (int l = 0; l <= L; ++l)
+        if (dims[l] > dmax) dmax = dims[l];
+    if (agg_build(model, n, rowptr, colidx, &op)) goto done;
     size_t gsz = (size_t)(n * dmax > 0 ? n * dmax : 1) * sizeof(double);
-    if (do_backward) {
-        G = (double *)malloc(gsz);
-        dY = (double *)malloc(gsz);
-        dZ = (double *)malloc(gsz);
-        Gprev = (double *)malloc(gsz);
-        if (!G || !dY || !dZ || !Gprev) goto done;
-    }
-    *loss = oracle_loss(n, dims[L], act[L - 1], labels, mask, do_backward ? G : NULL);
-    if (!do_backward) {
-        rc = 0;
-        goto done;
-    }
+    G = (double *)malloc(gsz);
+    dY = (double *)malloc(gsz);
+    dZ = (double *)malloc(gsz);
+    Gprev = (double *)malloc(gsz);
+    if (!G || !dY || !dZ || !Gprev) goto done;
+    *loss = oracle_loss(n, dims[L], act[L - 1], labels, mask, G);
 
-    /* ---- backward, layers L .. 1 ---- */
     for (int l = L - 1; l >= 0; --l) {
         int64_t din = dims[l], dout = dims[l + 1];
         const double *Ain = l == 0 ? X : act[l - 1];
+        const uint8_t *on = (relu_on && l < L - 1) ? relu_on[l] : NULL;
         if (gact && gact[l]) memcpy(gact[l], G, (size_t)(n * dout) * sizeof(double));
         /* through the activation: relu on hidden layers, identity on the last */
 #pragma omp parallel for schedule(static)
-        for (int64_t i = 0; i < n * dout; ++i)
-            dY[i] = (l < L - 1 && !(act[l][i] > 0.0)) ? 0.0 : G[i];
+        for (int64_t i = 0; i < n * dout; ++i) {
+            int pass = 1;
+            if (l < L - 1) pass = on ? (on[i] != 0) : (act[l][i] > 0.0);
+            dY[i] = pass ? G[i] : 0.0;
+        }
         if (gb && gb[l])
             for (int64_t c = 0; c < dout; ++c) {
                 double s = 0.0;
                 for (int64_t v = 0; v < n; ++v) s += dY[v * dout + c];
                 gb[l][c] = s;
             }
-        if (gW && gW[l]) matmul_tn(n, din, dout, Z[l], dY, gW[l]);
+        if (gW && gW[l]) matmul_tn(n, din, dout, zagg[l], dY, gW[l]);
         if (model == ORACLE_SAGE && gWs && gWs[l]) matmul_tn(n, din, dout, Ain, dY, gWs[l]);
         if (l >= 1 || gX) {
             matmul_nt(n, dout, din, dY, W[l], dZ, 0);
@@ -354,9 +367,6 @@ int oracle_epoch(int model, int64_t n, const int64_t *rowptr, const int32_t *col
     if (gX) memcpy(gX, G, (size_t)(n * dims[0]) * sizeof(double));
     rc = 0;
 done:
-    if (Z)
-        for (int l = 0; l < L; ++l) free(Z[l]);
-    free(Z);
     free(G);
     free(dY);
     free(dZ);

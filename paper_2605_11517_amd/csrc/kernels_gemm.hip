@@ -52,18 +52,19 @@ __device__ inline void load_kfast(const float* __restrict__ p, int64_t ld, int64
         r[i] = v;
     }
 }
+// k-fast tiles are kept [x][k] in LDS (row stride BK + 4 floats): one 16-byte store per
+// register, and an MFMA lane later fetches eight consecutive k of its row with two 16-byte
+// reads.
+constexpr int KF_LD = 20;   // BK + 4
 template <int BT>
-__device__ inline void store_kfast(float (*S)[BT + PAD], const float4 (&r)[BT / 64])
+__device__ inline void store_kfast(float* S, const float4 (&r)[BT / 64])
 {
     const int t = threadIdx.x;
     const int kq = (t & 3) * 4;
 #pragma unroll
     for (int i = 0; i < BT / 64; ++i) {
         const int x = (t >> 2) + 64 * i;
-        S[kq + 0][x] = r[i].x;
-        S[kq + 1][x] = r[i].y;
-        S[kq + 2][x] = r[i].z;
-        S[kq + 3][x] = r[i].w;
+        *reinterpret_cast<float4*>(S + x * KF_LD + kq) = r[i];
     }
 }
 
@@ -97,7 +98,7 @@ __device__ inline void load_kslow(const float* __restrict__ p, int64_t ld, int64
     }
 }
 template <int BT>
-__device__ inline void store_kslow(float (*S)[BT + PAD], const float4 (&r)[BT / 64])
+__device__ inline void store_kslow(float* S, const float4 (&r)[BT / 64])
 {
     constexpr int TPR = BT / 4;
     constexpr int KPP = kThreads / TPR;
@@ -105,7 +106,25 @@ __device__ inline void store_kslow(float (*S)[BT + PAD], const float4 (&r)[BT / 
     const int fq = (t % TPR) * 4;
 #pragma unroll
     for (int i = 0; i < BT / 64; ++i)
-        *reinterpret_cast<float4*>(&S[t / TPR + KPP * i][fq]) = r[i];
+        *reinterpret_cast<float4*>(S + (t / TPR + KPP * i) * (BT + PAD) + fq) = r[i];
+}
+
+// Fragment of one operand for a whole BK = 16 tile: f[j] is the value this lane feeds to the
+// j-th MFMA k-step.  The two half-waves of a 32x32x2 MFMA supply k = 0 and k = 1 of a step;
+// here half h supplies k = 8 h + j of the tile at step j (the k order inside a tile is free
+// as long as A and B agree), which makes a k-fast row fragment eight consecutive floats.
+template <int BT, bool KFAST>
+__device__ inline void load_fragment(const float* S, int x, int half, float (&f)[8])
+{
+    if (KFAST) {
+        const float4 lo = *reinterpret_cast<const float4*>(S + x * KF_LD + 8 * half);
+        const float4 hi = *reinterpret_cast<const float4*>(S + x * KF_LD + 8 * half + 4);
+        f[0] = lo.x; f[1] = lo.y; f[2] = lo.z; f[3] = lo.w;
+        f[4] = hi.x; f[5] = hi.y; f[6] = hi.z; f[7] = hi.w;
+    } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) f[j] = S[(8 * half + j) * (BT + PAD) + x];
+    }
 }
 
 struct GemmArgs {
@@ -124,13 +143,15 @@ struct GemmArgs {
 
 // A_KFAST: A(m,k) = a[m*lda + k]   (else a[k*lda + m])
 // B_KFAST: B(k,n) = b[n*ldb + k]   (else b[k*ldb + n])
-template <int BM, int BN, bool A_KFAST, bool B_KFAST, bool VEC>
+template <int BM, int BN, bool A_KFAST, bool B_KFAST, bool VEC_A, bool VEC_B>
 __global__ __launch_bounds__(kThreads) void k_gemm(const GemmArgs g)
 {
     constexpr int WM = BM / 2, WN = BN / 2;   // wave tile
     constexpr int TM = WM / 32, TN = WN / 32; // 32x32 MFMA tiles per wave
-    __shared__ float As[2][BK][BM + PAD];
-    __shared__ float Bs[2][BK][BN + PAD];
+    constexpr int A_TILE = A_KFAST ? BM * KF_LD : BK * (BM + PAD);
+    constexpr int B_TILE = B_KFAST ? BN * KF_LD : BK * (BN + PAD);
+    __shared__ __attribute__((aligned(16))) float As[2][A_TILE];
+    __shared__ __attribute__((aligned(16))) float Bs[2][B_TILE];
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -163,10 +184,10 @@ __global__ __launch_bounds__(kThreads) void k_gemm(const GemmArgs g)
         const int seg = t < tiles0 ? 0 : 1;
         const int64_t k0 = seg == 0 ? kbeg + t * BK : (t - tiles0) * BK;
         const int64_t kend = seg == 0 ? kend0 : (int64_t)g.kseg[1];
-        if (A_KFAST) load_kfast<BM, VEC>(g.a[seg].p, g.a[seg].ld, m0, g.m, (int32_t)k0, (int32_t)kend, ra);
-        else load_kslow<BM, VEC>(g.a[seg].p, g.a[seg].ld, k0, kend, m0, g.m, ra);
-        if (B_KFAST) load_kfast<BN, VEC>(g.b[seg].p, g.b[seg].ld, n0, g.n, (int32_t)k0, (int32_t)kend, rb);
-        else load_kslow<BN, VEC>(g.b[seg].p, g.b[seg].ld, k0, kend, n0, g.n, rb);
+        if (A_KFAST) load_kfast<BM, VEC_A>(g.a[seg].p, g.a[seg].ld, m0, g.m, (int32_t)k0, (int32_t)kend, ra);
+        else load_kslow<BM, VEC_A>(g.a[seg].p, g.a[seg].ld, k0, kend, m0, g.m, ra);
+        if (B_KFAST) load_kfast<BN, VEC_B>(g.b[seg].p, g.b[seg].ld, n0, g.n, (int32_t)k0, (int32_t)kend, rb);
+        else load_kslow<BN, VEC_B>(g.b[seg].p, g.b[seg].ld, k0, kend, n0, g.n, rb);
     };
     auto store_tile = [&](int buf) {
         if (A_KFAST) store_kfast<BM>(As[buf], ra); else store_kslow<BM>(As[buf], ra);
@@ -181,20 +202,19 @@ __global__ __launch_bounds__(kThreads) void k_gemm(const GemmArgs g)
     for (int64_t t = 0; t < ntiles; ++t) {
         const int buf = (int)(t & 1);
         if (t + 1 < ntiles) load_tile(t + 1);
-        const int kl = lane >> 5, xl = lane & 31;
+        const int half = lane >> 5, xl = lane & 31;
+        float af[TM][8], bf[TN][8];
 #pragma unroll
-        for (int kk = 0; kk < BK; kk += 2) {
-            float av[TM], bv[TN];
+        for (int i = 0; i < TM; ++i) load_fragment<BM, A_KFAST>(As[buf], wm0 + 32 * i + xl, half, af[i]);
 #pragma unroll
-            for (int i = 0; i < TM; ++i) av[i] = As[buf][kk + kl][wm0 + 32 * i + xl];
+        for (int j = 0; j < TN; ++j) load_fragment<BN, B_KFAST>(Bs[buf], wn0 + 32 * j + xl, half, bf[j]);
 #pragma unroll
-            for (int j = 0; j < TN; ++j) bv[j] = Bs[buf][kk + kl][wn0 + 32 * j + xl];
+        for (int st = 0; st < 8; ++st)
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
-        }
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i][st], bf[j][st], acc[i][j], 0, 0, 0);
         if (t + 1 < ntiles) store_tile(buf ^ 1);
         __syncthreads();
     }
@@ -263,34 +283,34 @@ template <bool A_KFAST, bool B_KFAST>
 void launch_gemm(const GemmArgs& g, int splits, hipStream_t s)
 {
     if (g.m <= 0 || g.n <= 0) return;
-    // float4 loads need 16-byte aligned rows, and the contiguous index of each operand (k for a
-    // k-fast operand, m or n otherwise) must consist of whole float4s
-    bool vec = true;
+    // float4 loads need 16-byte aligned rows, and the contiguous index of the operand (k for a
+    // k-fast operand, m or n otherwise) must consist of whole float4s; decided per operand
+    bool va = true, vb = true;
     for (int i = 0; i < 2; ++i) {
         if (g.kseg[i] == 0) continue;
-        vec = vec && aligned16(g.a[i].p) && aligned16(g.b[i].p) && g.a[i].ld % 4 == 0 &&
-              g.b[i].ld % 4 == 0;
-        if (A_KFAST || B_KFAST) vec = vec && g.kseg[i] % 4 == 0;
+        va = va && aligned16(g.a[i].p) && g.a[i].ld % 4 == 0 && (!A_KFAST || g.kseg[i] % 4 == 0);
+        vb = vb && aligned16(g.b[i].p) && g.b[i].ld % 4 == 0 && (!B_KFAST || g.kseg[i] % 4 == 0);
     }
-    if (!A_KFAST) vec = vec && g.m % 4 == 0;
-    if (!B_KFAST) vec = vec && g.n % 4 == 0;
+    if (!A_KFAST) va = va && g.m % 4 == 0;
+    if (!B_KFAST) vb = vb && g.n % 4 == 0;
     const bool big_m = g.m > 64, big_n = g.n > 64;
-#define GNN_GEMM(BM, BN, VEC)                                                                   \
-    hipLaunchKernelGGL((k_gemm<BM, BN, A_KFAST, B_KFAST, VEC>),                                 \
+#define GNN_GEMM(BM, BN, VA, VB)                                                                \
+    hipLaunchKernelGGL((k_gemm<BM, BN, A_KFAST, B_KFAST, VA, VB>),                              \
                        dim3((unsigned)((g.m + BM - 1) / BM), (unsigned)((g.n + BN - 1) / BN),   \
                             (unsigned)splits),                                                  \
                        dim3(kThreads), 0, s, g)
-    if (vec) {
-        if (big_m && big_n) GNN_GEMM(128, 128, true);
-        else if (big_m) GNN_GEMM(128, 64, true);
-        else if (big_n) GNN_GEMM(64, 128, true);
-        else GNN_GEMM(64, 64, true);
-    } else {
-        if (big_m && big_n) GNN_GEMM(128, 128, false);
-        else if (big_m) GNN_GEMM(128, 64, false);
-        else if (big_n) GNN_GEMM(64, 128, false);
-        else GNN_GEMM(64, 64, false);
-    }
+#define GNN_GEMM_TILE(VA, VB)                                     \
+    do {                                                          \
+        if (big_m && big_n) GNN_GEMM(128, 128, VA, VB);           \
+        else if (big_m) GNN_GEMM(128, 64, VA, VB);                \
+        else if (big_n) GNN_GEMM(64, 128, VA, VB);                \
+        else GNN_GEMM(64, 64, VA, VB);                            \
+    } while (0)
+    if (va && vb) GNN_GEMM_TILE(true, true);
+    else if (va) GNN_GEMM_TILE(true, false);
+    else if (vb) GNN_GEMM_TILE(false, true);
+    else GNN_GEMM_TILE(false, false);
+#undef GNN_GEMM_TILE
 #undef GNN_GEMM
 }
 

@@ -282,6 +282,37 @@ def test_thread_count_does_not_change_any_bit():
     assert a["loss"] == b["loss"]
 
 
+def test_supplied_activation_decision_is_used_as_given():
+    # the optional decision array replaces act > 0; checked against reverse mode written out
+    # with dense matrices and the same explicit masks
+    n, dims = 20, (4, 6, 5, 3)
+    rowptr, colidx = small_graph(n, 70, seed=12, symmetric=True, self_loops=False)
+    rng = np.random.default_rng(4)
+    X = rng.standard_normal((n, dims[0]))
+    y = rng.integers(0, dims[-1], n).astype(np.int32)
+    m = (rng.random(n) < 0.6).astype(np.uint8)
+    w = random_weights(dims, 8, sage=True)
+    f = og.forward("sage", rowptr, colidx, dims, X, w)
+    same = og.backward(f, y, m, relu_on=[(a > 0).astype(np.uint8) for a in f.act[:-1]])
+    plain = og.backward(f, y, m)
+    for key in ("gW", "gWs", "gb", "gact"):
+        for a, b in zip(same[key], plain[key]):
+            assert np.array_equal(a, b)
+    masks = [(rng.random(a.shape) < 0.5).astype(np.uint8) for a in f.act[:-1]]
+    got = og.backward(f, y, m, relu_on=masks)
+    S = dense_operator("sage", rowptr, colidx)
+    _, G = og.loss(f.act[-1], y, m)
+    acts = [X] + f.act
+    for l in (2, 1, 0):
+        dY = G * masks[l] if l < 2 else G
+        assert np.abs(got["gW"][l] - (S @ acts[l]).T @ dY).max() < 1e-13
+        assert np.abs(got["gWs"][l] - acts[l].T @ dY).max() < 1e-13
+        assert np.abs(got["gb"][l] - dY.sum(axis=0)).max() < 1e-13
+        G = S.T @ (dY @ w[l]["W"].T) + dY @ w[l]["Ws"].T
+        if l >= 1:
+            assert np.abs(got["gact"][l - 1] - G).max() < 1e-13
+
+
 def test_rel_err_helper():
     assert rel_err([1.0, 2.0], [1.0, 2.0]) == 0.0
     assert abs(rel_err([1.0, 2.2], [1.0, 2.0]) - 0.1) < 1e-12
