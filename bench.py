@@ -22,15 +22,17 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_F32_PEAK_TFLOPS = 157.3   # dense fp32 matrix cores
+MFMA_BF16_PEAK_TFLOPS = 2500.0 # dense bf16 matrix cores
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def algorithmic_bytes(stats, dims, model, n_parts):
+def algorithmic_bytes(stats, dims, model, n_parts, es=4):
     """HBM bytes the method has to move per epoch, by kernel class (lower bound: every needed
-    source row is read once per partition)."""
+    source row is read once per partition).  es = bytes per stored activation (4 fp32, 2 bf16);
+    gradients of activations are always fp32."""
     n, nnz, k = stats["n"], stats["nnz"], stats["k"]
     sum_r = n + stats["sum_boundary"]            # sum over partitions of |own_p| + |B_p|
     sum_b = stats["sum_boundary"]
@@ -39,15 +41,16 @@ def algorithmic_bytes(stats, dims, model, n_parts):
     out = {"gather": 0, "spmm": 0, "spmm_t": 0, "scatter": 0}
     for l in range(1, L + 1):
         d = dims[l - 1]
-        row = d * 4
+        row = d * es
+        grow = d * 4
         # forward + backward regather
         out["gather"] += 2 * (2 * sum_b * row + 4 * sum_b)
         # forward + recompute
         spmm = per_entry * nnz + 8 * (n + k) + sum_r * row + n * row + (4 * n if model == "sage" else 0)
         out["spmm"] += 2 * spmm
         if l >= 2:
-            out["spmm_t"] += 8 * nnz + 8 * (sum_r + k) + n * row + sum_r * row
-            out["scatter"] += 3 * sum_r * row + 4 * sum_b
+            out["spmm_t"] += 8 * nnz + 8 * (sum_r + k) + n * row + sum_r * grow
+            out["scatter"] += 3 * sum_r * grow + 4 * sum_b
     return out
 
 
@@ -130,7 +133,10 @@ def main():
     y, m = labels_and_mask(n, dims[-1], cfg["train_frac"], cfg["seed"])
     w = glorot_weights(dims, cfg["seed"], sage=(model == "sage"))
     t1 = time.perf_counter()
-    s = Session(model, dims, rowptr, colidx, cfg["k"], cfg["part"], cfg["seed"], X, w, y, m)
+    s = Session(model, dims, rowptr, colidx, cfg["k"], cfg["part"], cfg["seed"], X, w, y, m,
+                dtype=cfg["dtype"])
+    es = 2 if cfg["dtype"] == "bf16" else 4
+    mfma_peak = MFMA_BF16_PEAK_TFLOPS if cfg["dtype"] == "bf16" else MFMA_F32_PEAK_TFLOPS
     stats = s.ctx.get_stats()
     log("partitions built and bound: k=%d alpha=%.3f sum_boundary=%d (%.1f s)" % (
         stats["k"], stats["sum_required"] / n, stats["sum_boundary"], time.perf_counter() - t1))
@@ -172,14 +178,14 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": cfg["dtype"], "data": "synthetic",
         "config": {"workload": args.workload, "n": n, "operator_entries": nnz, "model": model,
                    "dims": list(dims), "k": stats["k"], "partitioner": cfg["part"],
                    "alpha": stats["sum_required"] / n, "sum_boundary": stats["sum_boundary"]},
         "loss": loss,
     }
     if prof:
-        ab = algorithmic_bytes(stats, dims, model, stats["k"])
+        ab = algorithmic_bytes(stats, dims, model, stats["k"], es)
         fl = gemm_flops(stats, dims, model)
         classes = {}
         for name, (ms, launches) in prof.items():
@@ -189,7 +195,7 @@ def main():
                 e["frac_hbm_peak"] = e["algorithmic_GBps"] / HBM_PEAK_GBS
             if name in fl and ms > 0:
                 e["TFLOPps"] = fl[name] * args.steps / (ms * 1e-3) / 1e12
-                e["frac_mfma_f32_peak"] = e["TFLOPps"] / MFMA_F32_PEAK_TFLOPS
+                e["frac_mfma_peak"] = e["TFLOPps"] / mfma_peak
             classes[name] = e
         out["kernel_classes"] = classes
         sp_ms, sp_launches = prof["spmm"]
@@ -212,7 +218,7 @@ def main():
                 tot_l = sum(r["launches"] for r in rows)
                 traffic = sum(r["bytes_per_launch"] * r["launches"] for r in rows) / tot_l
         L = len(dims) - 1
-        upper = sum((2 if l == 0 else 3) * (stats["nnz"] * (4 + dims[l] * 4) + n * dims[l] * 4)
+        upper = sum((2 if l == 0 else 3) * (stats["nnz"] * (4 + dims[l] * es) + n * dims[l] * es)
                     for l in range(L))
         out["roofline"] = {
             "kernel": "k_spmm_items (aggregation over T_p and T_p^T: forward, recompute, transposed)",

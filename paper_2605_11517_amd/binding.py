@@ -221,13 +221,15 @@ class Session:
     them.  Results are read back in original vertex order."""
 
     def __init__(self, model, dims, rowptr, colidx, k, part_mode, seed, X, weights, labels,
-                 train_mask, has_bias=True, user_part=None, device="cuda:0"):
+                 train_mask, has_bias=True, user_part=None, device="cuda:0", dtype="f32"):
         import torch
         self.torch = torch
         if not torch.cuda.is_available():
             raise RuntimeError("gnnmi needs a GPU: torch.cuda.is_available() is False")
         self.dev = torch.device(device)
-        self.ctx = Context(model, dims, has_bias=has_bias)
+        self.bf16 = dtype in ("bf16", GNN_BF16)
+        store = torch.bfloat16 if self.bf16 else torch.float32
+        self.ctx = Context(model, dims, dtype=GNN_BF16 if self.bf16 else GNN_F32, has_bias=has_bias)
         self.ctx.build_partitions(rowptr, colidx, k, part_mode, seed, user_part)
         self.model = _MODEL.get(model, model)
         self.dims = list(dims)
@@ -237,10 +239,13 @@ class Session:
         t = torch
         stream = self.stream
         # inputs: upload in original order, permute on the device
-        self.feat = self._to_library(t.from_numpy(np.ascontiguousarray(X, dtype=np.float32)))
+        # bf16 storage: values are converted once here (round to nearest even)
+        self.feat = self._to_library(
+            t.from_numpy(np.ascontiguousarray(X, dtype=np.float32)).to(store))
         self.labels = self._to_library(t.from_numpy(np.ascontiguousarray(labels, dtype=np.int32)))
         self.mask = self._to_library(t.from_numpy(np.ascontiguousarray(train_mask, dtype=np.uint8)))
-        self.act = [t.zeros((self.n, dims[l + 1]), dtype=t.float32, device=self.dev)
+        self.act = [t.zeros((self.n, dims[l + 1]), device=self.dev,
+                            dtype=store if l < self.L - 1 else t.float32)   # logits stay fp32
                     for l in range(self.L)]
         self.gact = [t.zeros((self.n, dims[l + 1]), dtype=t.float32, device=self.dev)
                      for l in range(self.L)]
@@ -252,8 +257,10 @@ class Session:
                     and (key != "b" or has_bias)
                 if use:
                     wt = t.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(self.dev)
+                    if key != "b":
+                        wt = wt.to(store)
                     self.w.append(wt)
-                    self.gw.append(t.zeros_like(wt))
+                    self.gw.append(t.zeros(wt.shape, dtype=t.float32, device=self.dev))
                 else:
                     self.w.append(None)
                     self.gw.append(None)
@@ -287,7 +294,7 @@ class Session:
         row_bytes = dev_tensor.element_size() * (dev_tensor.shape[1] if dev_tensor.dim() == 2 else 1)
         self.ctx.permute_rows(dev_tensor.data_ptr(), dst.data_ptr(), row_bytes, False, self.stream)
         t.cuda.synchronize()
-        return dst.cpu().numpy()
+        return dst.float().cpu().numpy()
 
     def epoch(self):
         return self.ctx.epoch(self.stream)

@@ -56,9 +56,10 @@ struct gnn_ctx {
     DevMeta D;
     Workspace ws;
     // bound buffers
-    const float* feat = nullptr;
-    std::vector<float*> act, gact;
-    std::vector<const float*> w;
+    const char* feat = nullptr;          // dtype of the context
+    std::vector<char*> act;              // act[l-1]: dtype for l < L, fp32 for l = L
+    std::vector<float*> gact;
+    std::vector<const char*> w;          // W, W_s: dtype; b: fp32
     std::vector<float*> gw;
     const int32_t* labels = nullptr;
     const uint8_t* mask = nullptr;
@@ -82,7 +83,14 @@ struct gnn_ctx {
         err = msg;
         return st;
     }
-    const float* layer_input(int32_t layer) const { return layer == 1 ? feat : act[(size_t)layer - 2]; }
+    bool bf16() const { return dtype == GNN_BF16; }
+    int64_t es() const { return dtype == GNN_BF16 ? 2 : 4; }   // bytes per stored activation/weight
+    // rows [r0, ...) of the input of `layer` (A^{layer-1}), width d
+    const char* layer_input(int32_t layer, int64_t r0 = 0) const
+    {
+        const char* base = layer == 1 ? feat : act[(size_t)layer - 2];
+        return base + r0 * (int64_t)dims[(size_t)layer - 1] * es();
+    }
 };
 
 namespace {
@@ -269,19 +277,19 @@ void run_spmm_fwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
     const HostMeta& M = c->M;
     const int64_t r0 = M.off[(size_t)p], np = M.off[(size_t)p + 1] - r0;
     const int32_t din = c->dims[(size_t)layer - 1];
-    const float* in = c->layer_input(layer);
     const SpmmItems items = plan_items(M.plan_fwd, c->D.fwd, p);
     const float* rscale = c->D.rscale ? c->D.rscale + r0 : nullptr;
-    float* Z = (float*)(c->scratch + c->ws.z);
+    void* Z = c->scratch + c->ws.z;
     float* segpart = (float*)(c->scratch + c->ws.segpart);
+    const int b16 = c->bf16() ? 1 : 0;
     {
         Timed t(c, s, GNN_K_SPMM);
-        launch_spmm(c->D.rp + r0, c->D.lcol, c->D.ew, rscale, in + r0 * din, np,
-                    (const float*)c->staging, Z, np, din, items, segpart, s);
+        launch_spmm(c->D.rp + r0, c->D.lcol, c->D.ew, rscale, c->layer_input(layer, r0), np,
+                    c->staging, Z, np, din, b16, b16, items, segpart, s);
     }
     if (items.nlong > 0) {
         Timed t(c, s, GNN_K_SPMM_REDUCE);
-        launch_spmm_reduce(rscale, Z, din, items, segpart, s);
+        launch_spmm_reduce(rscale, Z, din, b16, items, segpart, s);
     }
 }
 
@@ -303,7 +311,6 @@ gnn_status gnn_create(const gnn_config* cfg, gnn_ctx** out)
         if (cfg->dims[l] < 1 || cfg->dims[l] > (1 << 20)) return bad(GNN_EINVAL, "layer width out of range");
     if (cfg->has_bias != 0 && cfg->has_bias != 1) return bad(GNN_EINVAL, "has_bias must be 0 or 1");
     if (cfg->hbm_budget_bytes < 0) return bad(GNN_EINVAL, "hbm_budget_bytes must be >= 0");
-    if (cfg->dtype == GNN_BF16) return bad(GNN_EUNSUPPORTED, "bf16 storage is not implemented yet");
     if (cfg->hbm_budget_bytes != 0)
         return bad(GNN_EUNSUPPORTED, "streaming from pinned host memory is not implemented yet");
     gnn_ctx* c = new (std::nothrow) gnn_ctx();
@@ -423,16 +430,16 @@ gnn_status gnn_bind(gnn_ctx* c, const void* feat, void* const* act, void* const*
         return c->fail(GNN_EINVAL, "feat, staging and scratch must be 16-byte aligned");
     gnn_status st = ensure_device(c);
     if (st != GNN_OK) return st;
-    c->feat = (const float*)feat;
+    c->feat = (const char*)feat;
     c->act.assign((size_t)L, nullptr);
     c->gact.assign((size_t)L, nullptr);
     c->w.assign((size_t)3 * L, nullptr);
     c->gw.assign((size_t)3 * L, nullptr);
     for (int32_t l = 0; l < L; ++l) {
-        c->act[(size_t)l] = (float*)act[l];
+        c->act[(size_t)l] = (char*)act[l];
         c->gact[(size_t)l] = (float*)grad_act[l];
         for (int j = 0; j < 3; ++j) {
-            c->w[(size_t)(3 * l + j)] = (const float*)weights[3 * l + j];
+            c->w[(size_t)(3 * l + j)] = (const char*)weights[3 * l + j];
             c->gw[(size_t)(3 * l + j)] = (float*)grad_w[3 * l + j];
         }
     }
@@ -470,7 +477,7 @@ gnn_status gnn_gather_boundary(gnn_ctx* c, int32_t layer, int32_t p, void* strea
     hipStream_t s = (hipStream_t)stream;
     const HostMeta& M = c->M;
     const int64_t b0 = M.boff[(size_t)p], nb = M.boff[(size_t)p + 1] - b0;
-    const int64_t row_bytes = (int64_t)c->dims[(size_t)layer - 1] * 4;
+    const int64_t row_bytes = (int64_t)c->dims[(size_t)layer - 1] * c->es();
     {
         Timed t(c, s, GNN_K_GATHER);
         launch_gather_rows(c->layer_input(layer), c->D.bnd + b0, c->staging, nb, row_bytes, s);
@@ -491,23 +498,35 @@ gnn_status gnn_layer_fwd(gnn_ctx* c, int32_t layer, int32_t p, void* stream)
     const HostMeta& M = c->M;
     const int64_t r0 = M.off[(size_t)p], np = M.off[(size_t)p + 1] - r0;
     const int32_t din = c->dims[(size_t)layer - 1], dout = c->dims[(size_t)layer];
-    const float* in = c->layer_input(layer);
-    float* Z = (float*)(c->scratch + c->ws.z);
     run_spmm_fwd(c, layer, p, s);
     {
         Timed t(c, s, GNN_K_GEMM_FWD);
-        GemmSeg seg[2];
-        seg[0].a = Z; seg[0].lda = din; seg[0].b = c->w[(size_t)3 * (layer - 1)]; seg[0].ldb = dout; seg[0].k = din;
-        int nseg = 1;
-        if (c->model == GNN_SAGE_MEAN) {
-            seg[1].a = in + r0 * din; seg[1].lda = din;
-            seg[1].b = c->w[(size_t)3 * (layer - 1) + 1]; seg[1].ldb = dout; seg[1].k = din;
-            nseg = 2;
-        }
         GemmEpilogue ep;
-        ep.bias = c->has_bias ? c->w[(size_t)3 * (layer - 1) + 2] : nullptr;
+        ep.bias = c->has_bias ? (const float*)c->w[(size_t)3 * (layer - 1) + 2] : nullptr;
         ep.relu = layer < c->L ? 1 : 0;
-        launch_gemm_nn(seg, nseg, c->act[(size_t)layer - 1] + r0 * dout, dout, np, dout, ep, s);
+        const bool sage = c->model == GNN_SAGE_MEAN;
+        if (!c->bf16()) {
+            GemmSeg seg[2];
+            seg[0].a = (const float*)(c->scratch + c->ws.z); seg[0].lda = din;
+            seg[0].b = (const float*)c->w[(size_t)3 * (layer - 1)]; seg[0].ldb = dout; seg[0].k = din;
+            if (sage) {
+                seg[1].a = (const float*)c->layer_input(layer, r0); seg[1].lda = din;
+                seg[1].b = (const float*)c->w[(size_t)3 * (layer - 1) + 1]; seg[1].ldb = dout; seg[1].k = din;
+            }
+            launch_gemm_nn(seg, sage ? 2 : 1, (float*)c->act[(size_t)layer - 1] + r0 * dout, dout, np,
+                           dout, ep, s);
+        } else {
+            GemmSegBf16 seg[2];
+            seg[0].a = c->scratch + c->ws.z; seg[0].lda = din;
+            seg[0].b = c->w[(size_t)3 * (layer - 1)]; seg[0].ldb = dout; seg[0].k = din;
+            if (sage) {
+                seg[1].a = c->layer_input(layer, r0); seg[1].lda = din;
+                seg[1].b = c->w[(size_t)3 * (layer - 1) + 1]; seg[1].ldb = dout; seg[1].k = din;
+            }
+            const int out_b16 = layer < c->L ? 1 : 0;      // logits stay fp32
+            char* out = c->act[(size_t)layer - 1] + r0 * (int64_t)dout * (out_b16 ? 2 : 4);
+            launch_gemm_bf16_nn(seg, sage ? 2 : 1, out, out_b16, dout, np, dout, ep, s);
+        }
     }
     c->fwd_done[(size_t)(layer - 1) * (size_t)M.k + (size_t)p] = 1;
     return check_launch(c, "gnn_layer_fwd");
@@ -523,7 +542,7 @@ gnn_status gnn_loss(gnn_ctx* c, void* stream)
     float* scal = (float*)(c->scratch + c->ws.scalars);
     {
         Timed t(c, s, GNN_K_LOSS);
-        launch_loss(c->act[(size_t)c->L - 1], c->labels, c->mask, c->gact[(size_t)c->L - 1], c->M.n,
+        launch_loss((const float*)c->act[(size_t)c->L - 1], c->labels, c->mask, c->gact[(size_t)c->L - 1], c->M.n,
                     c->dims[(size_t)c->L], (unsigned long long*)(scal + 16),
                     (float*)(c->scratch + c->ws.losspart), scal, s);
     }
@@ -560,18 +579,19 @@ gnn_status gnn_layer_bwd(gnn_ctx* c, int32_t layer, int32_t p, void* stream)
     const int64_t r0 = M.off[(size_t)p], np = M.off[(size_t)p + 1] - r0;
     const int64_t nb = M.boff[(size_t)p + 1] - M.boff[(size_t)p];
     const int32_t din = c->dims[(size_t)layer - 1], dout = c->dims[(size_t)layer];
-    const float* in = c->layer_input(layer);
-    const float* W = c->w[(size_t)3 * (layer - 1)];
-    const float* Ws = c->w[(size_t)3 * (layer - 1) + 1];
+    const char* W = c->w[(size_t)3 * (layer - 1)];
+    const char* Ws = c->w[(size_t)3 * (layer - 1) + 1];
     float* gW = c->gw[(size_t)3 * (layer - 1)];
     float* gWs = c->gw[(size_t)3 * (layer - 1) + 1];
     float* gb = c->has_bias ? c->gw[(size_t)3 * (layer - 1) + 2] : nullptr;
-    float* Z = (float*)(c->scratch + c->ws.z);
-    float* dYbuf = (float*)(c->scratch + c->ws.dy);
-    float* dZ = (float*)(c->scratch + c->ws.dz);
+    char* Z = c->scratch + c->ws.z;
+    char* dYbuf = c->scratch + c->ws.dy;
+    char* dZ = c->scratch + c->ws.dz;
     float* dGA = (float*)(c->scratch + c->ws.dga);
     float* partial = (float*)(c->scratch + c->ws.partial);
     float* colpart = (float*)(c->scratch + c->ws.colpart);
+    const bool b16 = c->bf16();
+    const bool sage = c->model == GNN_SAGE_MEAN;
 
     // write-back buffer initialisation: first partition of this layer since gnn_loss
     if (layer >= 2 && c->bwd_done[(size_t)layer] == 0) {
@@ -580,11 +600,16 @@ gnn_status gnn_layer_bwd(gnn_ctx* c, int32_t layer, int32_t p, void* stream)
     }
     // activation backward: dY = grad A ⊙ [A > 0] on hidden layers, grad A itself on the last
     const float* g = c->gact[(size_t)layer - 1] + r0 * dout;
-    const float* dY = g;
+    const char* dY = (const char*)g;
     {
         Timed t(c, s, GNN_K_ACT_BWD);
-        if (layer < L) {
-            launch_act_bwd(g, c->act[(size_t)layer - 1] + r0 * dout, dYbuf, np, dout, gb, colpart, s);
+        if (b16) {
+            const char* a = layer < L ? c->act[(size_t)layer - 1] + r0 * (int64_t)dout * 2 : nullptr;
+            launch_act_bwd_bf16(g, a, dYbuf, np, dout, gb, colpart, s);
+            dY = dYbuf;
+        } else if (layer < L) {
+            launch_act_bwd(g, (const float*)c->act[(size_t)layer - 1] + r0 * dout, (float*)dYbuf, np,
+                           dout, gb, colpart, s);
             dY = dYbuf;
         } else {
             launch_act_bwd(g, nullptr, nullptr, np, dout, gb, colpart, s);
@@ -595,16 +620,25 @@ gnn_status gnn_layer_bwd(gnn_ctx* c, int32_t layer, int32_t p, void* stream)
     // weight gradients, summed over partitions
     {
         Timed t(c, s, GNN_K_GEMM_DW);
-        launch_gemm_tn(Z, din, dY, dout, gW, dout, din, dout, np, partial, s);
-        if (c->model == GNN_SAGE_MEAN)
-            launch_gemm_tn(in + r0 * din, din, dY, dout, gWs, dout, din, dout, np, partial, s);
+        if (b16) {
+            launch_gemm_bf16_tn(Z, din, dY, dout, gW, dout, din, dout, np, partial, s);
+            if (sage)
+                launch_gemm_bf16_tn(c->layer_input(layer, r0), din, dY, dout, gWs, dout, din, dout, np,
+                                    partial, s);
+        } else {
+            launch_gemm_tn((const float*)Z, din, (const float*)dY, dout, gW, dout, din, dout, np, partial, s);
+            if (sage)
+                launch_gemm_tn((const float*)c->layer_input(layer, r0), din, (const float*)dY, dout, gWs,
+                               dout, din, dout, np, partial, s);
+        }
     }
     if (layer >= 2) {
         float* gprev = c->gact[(size_t)layer - 2];
         {
             Timed t(c, s, GNN_K_GEMM_DZ);
             GemmEpilogue ep;
-            launch_gemm_nt(dY, dout, W, dout, dZ, din, np, din, dout, ep, s);
+            if (b16) launch_gemm_bf16_nt(dY, dout, W, dout, dZ, 1, din, np, din, dout, ep, s);
+            else launch_gemm_nt((const float*)dY, dout, (const float*)W, dout, (float*)dZ, din, np, din, dout, ep, s);
         }
         {
             const int64_t t0 = M.toff[(size_t)p];
@@ -613,22 +647,23 @@ gnn_status gnn_layer_bwd(gnn_ctx* c, int32_t layer, int32_t p, void* stream)
             {
                 Timed t(c, s, GNN_K_SPMM_T);
                 launch_spmm(c->D.trp + t0, c->D.tcol, c->D.tw, nullptr, dZ, np, nullptr, dGA, np + nb,
-                            din, items, segpart, s);
+                            din, b16 ? 1 : 0, 0, items, segpart, s);
             }
             if (items.nlong > 0) {
                 Timed t(c, s, GNN_K_SPMM_REDUCE);
-                launch_spmm_reduce(nullptr, dGA, din, items, segpart, s);
+                launch_spmm_reduce(nullptr, dGA, din, 0, items, segpart, s);
             }
         }
         {
             Timed t(c, s, GNN_K_SCATTER);
             launch_scatter_add(dGA, np + nb, np, r0, c->D.bnd + M.boff[(size_t)p], gprev, din, s);
         }
-        if (c->model == GNN_SAGE_MEAN) {
+        if (sage) {
             Timed t(c, s, GNN_K_GEMM_DZ);
             GemmEpilogue ep;
             ep.accumulate = 1;
-            launch_gemm_nt(dY, dout, Ws, dout, gprev + r0 * din, din, np, din, dout, ep, s);
+            if (b16) launch_gemm_bf16_nt(dY, dout, Ws, dout, gprev + r0 * din, 0, din, np, din, dout, ep, s);
+            else launch_gemm_nt((const float*)dY, dout, (const float*)Ws, dout, gprev + r0 * din, din, np, din, dout, ep, s);
         }
     }
     c->bwd_done[(size_t)layer] += 1;

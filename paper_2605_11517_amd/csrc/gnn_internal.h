@@ -91,12 +91,15 @@ struct SpmmItems {
     const int32_t* long_nseg = nullptr;
     int64_t nlong = 0;
 };
+// a_rows / b_rows hold fp32 (in_bf16 = 0) or bfloat16 rows; out is fp32 or bfloat16; the sums
+// and `partial` are always fp32.
 void launch_spmm(const int64_t* rp, const int32_t* col, const float* w, const float* rowscale,
-                 const float* a_rows, int64_t n_a, const float* b_rows, float* out,
-                 int64_t nrows, int32_t d, const SpmmItems& items, float* partial, hipStream_t s);
+                 const void* a_rows, int64_t n_a, const void* b_rows, void* out, int64_t nrows,
+                 int32_t d, int in_bf16, int out_bf16, const SpmmItems& items, float* partial,
+                 hipStream_t s);
 // second step of the aggregation: combines the segment partial sums of the long rows
-void launch_spmm_reduce(const float* rowscale, float* out, int32_t d, const SpmmItems& items,
-                        float* partial, hipStream_t s);
+void launch_spmm_reduce(const float* rowscale, void* out, int32_t d, int out_bf16,
+                        const SpmmItems& items, float* partial, hipStream_t s);
 
 // dst[map(i),:] += src[i,:] with map(i) = base_row + i for i < n_own, idx[i - n_own] otherwise.
 void launch_scatter_add(const float* src, int64_t nrows, int64_t n_own, int64_t base_row,
@@ -127,6 +130,32 @@ int gemm_tn_splits(int64_t kdim, int32_t m, int32_t n);
 void launch_gemm_tn(const float* a, int64_t lda, const float* b, int64_t ldb, float* c,
                     int64_t ldc, int32_t m, int32_t n, int64_t kdim, float* partial,
                     hipStream_t s);
+
+// bfloat16 operands (raw 16-bit storage), fp32 accumulation; C is fp32 or bfloat16.
+struct GemmSegBf16 {
+    const void* a = nullptr;
+    int64_t lda = 0;
+    const void* b = nullptr;
+    int64_t ldb = 0;
+    int32_t k = 0;
+};
+void launch_gemm_bf16_nn(const GemmSegBf16* segs, int nseg, void* c, int out_bf16, int64_t ldc,
+                         int64_t m, int32_t n, const GemmEpilogue& ep, hipStream_t s);
+void launch_gemm_bf16_nt(const void* a, int64_t lda, const void* b, int64_t ldb, void* c,
+                         int out_bf16, int64_t ldc, int64_t m, int32_t n, int32_t k,
+                         const GemmEpilogue& ep, hipStream_t s);
+void launch_gemm_bf16_tn(const void* a, int64_t lda, const void* b, int64_t ldb, float* c,
+                         int64_t ldc, int32_t m, int32_t n, int64_t kdim, float* partial,
+                         hipStream_t s);
+// c[i] += sum over splits of partial[split * stride + i], splits in ascending order
+void launch_reduce_partials(const float* partial, int splits, int64_t stride, float* c, int64_t ldc,
+                            int32_t m, int32_t n, hipStream_t s);
+void launch_to_bf16(const float* src, void* dst, int64_t n, hipStream_t s);
+
+// bfloat16 variant of the activation backward: g fp32, act bfloat16 (or null), dy bfloat16
+// (always written, because the contractions that follow take bfloat16 operands).
+void launch_act_bwd_bf16(const float* g, const void* act, void* dy, int64_t rows, int32_t d,
+                         float* gb, float* partial, hipStream_t s);
 
 // dy = g * (act > 0) (or dy = g when act == null); colsum partials then gb += colsum.
 // `partial` holds ceil(rows / 64) * d floats.

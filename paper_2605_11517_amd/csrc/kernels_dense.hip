@@ -187,6 +187,44 @@ __global__ __launch_bounds__(kBlock) void k_act_bwd_vec(const float* __restrict_
     }
 }
 
+// bfloat16 variant: g fp32, act bfloat16 (may be null), dy bfloat16 (always written).  One
+// thread per column walking the block's 256 rows; consecutive threads touch consecutive
+// columns, so every access is coalesced.
+__global__ __launch_bounds__(kBlock) void k_act_bwd_bf16(const float* __restrict__ g,
+                                                         const uint16_t* __restrict__ act,
+                                                         uint16_t* __restrict__ dy, int64_t rows,
+                                                         int32_t d, float* __restrict__ partial)
+{
+    const int64_t r0 = (int64_t)blockIdx.x * kRowsPerBlockAct;
+    const int64_t r1 = r0 + kRowsPerBlockAct < rows ? r0 + kRowsPerBlockAct : rows;
+    for (int32_t c = threadIdx.x; c < d; c += kBlock) {
+        float s = 0.f;
+        constexpr int U = 8;
+        for (int64_t r = r0; r < r1; r += U) {
+            float gv[U];
+            uint32_t av[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const bool in = r + u < r1;
+                gv[u] = in ? g[(r + u) * d + c] : 0.f;
+                av[u] = (in && act) ? (uint32_t)act[(r + u) * d + c] : 0x3F80u;   // 1.0
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                // positive bfloat16: sign bit clear and not zero
+                const bool pos = (av[u] & 0x8000u) == 0 && (av[u] & 0x7FFFu) != 0;
+                const float v = pos ? gv[u] : 0.f;
+                if (r + u < r1) {
+                    const uint32_t b = __float_as_uint(v);
+                    dy[(r + u) * d + c] = (uint16_t)((b + 0x7FFFu + ((b >> 16) & 1u)) >> 16);
+                }
+                s += v;
+            }
+        }
+        partial[(int64_t)blockIdx.x * d + c] = s;
+    }
+}
+
 // gb[c] += sum_b partial[b, c]: a block owns 32 columns; its 8 row groups walk the partial rows
 // 8 apart and are combined through LDS in a fixed order.
 __global__ __launch_bounds__(kBlock) void k_colsum_finish(const float* __restrict__ partial,
@@ -258,6 +296,18 @@ void launch_act_bwd(const float* g, const float* act, float* dy, int64_t rows, i
     if (gb)
         hipLaunchKernelGGL(k_colsum_finish, dim3((unsigned)((d + 31) / 32)), dim3(kBlock),
                            0, s, (const float*)partial, blocks, d, gb);
+}
+
+void launch_act_bwd_bf16(const float* g, const void* act, void* dy, int64_t rows, int32_t d,
+                         float* gb, float* partial, hipStream_t s)
+{
+    if (rows <= 0) return;
+    const int64_t blocks = (rows + kRowsPerBlockAct - 1) / kRowsPerBlockAct;
+    hipLaunchKernelGGL(k_act_bwd_bf16, dim3((unsigned)blocks), dim3(kBlock), 0, s, g,
+                       (const uint16_t*)act, (uint16_t*)dy, rows, d, partial);
+    if (gb)
+        hipLaunchKernelGGL(k_colsum_finish, dim3((unsigned)((d + 31) / 32)), dim3(kBlock), 0, s,
+                           (const float*)partial, blocks, d, gb);
 }
 
 }  // namespace gnnmi

@@ -374,9 +374,15 @@ void launch_gemm_tn(const float* a, int64_t lda, const float* b, int64_t ldb, fl
     g.split_chunk = chunk;
     g.split_stride = (int64_t)m * n;
     launch_gemm<false, false>(g, splits, s);
+    launch_reduce_partials(partial, splits, (int64_t)m * n, c, ldc, m, n, s);
+}
+
+void launch_reduce_partials(const float* partial, int splits, int64_t stride, float* c, int64_t ldc,
+                            int32_t m, int32_t n, hipStream_t s)
+{
     int64_t blocks = ((int64_t)m * n + 1023) / 1024;
-    hipLaunchKernelGGL(k_reduce_partials, dim3((unsigned)blocks), dim3(256),
-                       0, s, (const float*)partial, splits, (int64_t)m * n, c, ldc, m, n);
+    hipLaunchKernelGGL(k_reduce_partials, dim3((unsigned)blocks), dim3(256), 0, s, partial, splits,
+                       stride, c, ldc, m, n);
 }
 
 }  // namespace gnnmi

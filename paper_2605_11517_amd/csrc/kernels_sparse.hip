@@ -100,31 +100,78 @@ struct SpmmArgs {
     const int32_t* col;
     const float* w;
     const float* rowscale;
-    const float* a_rows;
+    const void* a_rows;     // element type TIn
     int64_t n_a;
-    const float* b_rows;
-    float* out;
-    int32_t d, ld;          // d: columns handled by this launch; ld: row stride
+    const void* b_rows;
+    void* out;              // element type TOut
+    int32_t d, ld;          // d: columns handled by this launch; ld: row stride (elements)
     SpmmItems it;
-    float* partial;
+    float* partial;         // always fp32
 };
 
-template <int G, int NV, bool VEC>
-__device__ inline void spmm_accumulate(const SpmmArgs& g, int64_t e_begin, int64_t e_end, int lane,
-                                       float (&acc)[NV][4])
+// 16-byte vectors of the storage types: 4 floats or 8 bfloat16 (kept as raw uint16_t).
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+    static constexpr int EPV = 4;
+    __device__ static inline void unpack(const uint4& v, float (&f)[4])
+    {
+        f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y);
+        f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
+    }
+    __device__ static inline uint4 pack(const float (&f)[4])
+    {
+        return make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]),
+                          __float_as_uint(f[3]));
+    }
+    __device__ static inline float load(const float* p) { return *p; }
+    __device__ static inline void store(float* p, float v) { *p = v; }
+};
+__device__ inline float bf16_to_float(uint32_t h) { return __uint_as_float(h << 16); }
+__device__ inline uint32_t float_to_bf16(float f)   // round to nearest even
 {
+    const uint32_t u = __float_as_uint(f);
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+template <> struct Elem<uint16_t> {
+    static constexpr int EPV = 8;
+    __device__ static inline void unpack(const uint4& v, float (&f)[8])
+    {
+        f[0] = bf16_to_float(v.x & 0xFFFFu); f[1] = bf16_to_float(v.x >> 16);
+        f[2] = bf16_to_float(v.y & 0xFFFFu); f[3] = bf16_to_float(v.y >> 16);
+        f[4] = bf16_to_float(v.z & 0xFFFFu); f[5] = bf16_to_float(v.z >> 16);
+        f[6] = bf16_to_float(v.w & 0xFFFFu); f[7] = bf16_to_float(v.w >> 16);
+    }
+    __device__ static inline uint4 pack(const float (&f)[8])
+    {
+        return make_uint4(float_to_bf16(f[0]) | (float_to_bf16(f[1]) << 16),
+                          float_to_bf16(f[2]) | (float_to_bf16(f[3]) << 16),
+                          float_to_bf16(f[4]) | (float_to_bf16(f[5]) << 16),
+                          float_to_bf16(f[6]) | (float_to_bf16(f[7]) << 16));
+    }
+    __device__ static inline float load(const uint16_t* p) { return bf16_to_float(*p); }
+    __device__ static inline void store(uint16_t* p, float v) { *p = (uint16_t)float_to_bf16(v); }
+};
+
+// acc[v][i] += sum over entries [e_begin, e_end) of w_e * src(col_e)[(v*G + lane%G)*EPV + i]
+template <typename TIn, int G, int NV, bool VEC>
+__device__ inline void spmm_accumulate(const SpmmArgs& g, int64_t e_begin, int64_t e_end, int lane,
+                                       float (&acc)[NV][Elem<TIn>::EPV])
+{
+    constexpr int EPV = Elem<TIn>::EPV;
     constexpr int S = kWave / G;
     constexpr int UNROLL = (NV == 1) ? 8 : 4;   // source rows in flight per slot
     const int slot = lane / G;
     const int gl = lane % G;
-    // column offsets of this lane's float4s; lanes past the row end read column 0 (their sums
+    const TIn* a_rows = static_cast<const TIn*>(g.a_rows);
+    const TIn* b_rows = static_cast<const TIn*>(g.b_rows);
+    // column offsets of this lane's vectors; lanes past the row end read column 0 (their sums
     // are never stored), so that every load below is unconditional and the compiler can keep
     // all of them in flight
-    int c4[NV];
+    int cv[NV];
 #pragma unroll
     for (int v = 0; v < NV; ++v) {
-        const int c = (v * G + gl) * 4;
-        c4[v] = c < g.d ? c : 0;
+        const int c = (v * G + gl) * EPV;
+        cv[v] = c < g.d ? c : 0;
     }
     // index/weight chunk of the first 64 entries; the next chunk is fetched while this one is
     // being consumed
@@ -143,7 +190,7 @@ __device__ inline void spmm_accumulate(const SpmmArgs& g, int64_t e_begin, int64
             my_w = g.w ? g.w[e0 + kWave + lane] : 1.f;
         }
         for (int j0 = 0; j0 < cnt; j0 += S * UNROLL) {
-            const float* src[UNROLL];
+            const TIn* src[UNROLL];
             float ww[UNROLL];
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
@@ -152,25 +199,25 @@ __device__ inline void spmm_accumulate(const SpmmArgs& g, int64_t e_begin, int64
                 const int32_t c = __shfl(cur_c, jj, kWave);
                 const float wt = __shfl(cur_w, jj, kWave);
                 ww[u] = j < cnt ? wt : 0.f;
-                src[u] = (c < g.n_a) ? g.a_rows + (int64_t)c * g.ld
-                                     : g.b_rows + ((int64_t)c - g.n_a) * g.ld;
+                src[u] = (c < g.n_a) ? a_rows + (int64_t)c * g.ld
+                                     : b_rows + ((int64_t)c - g.n_a) * g.ld;
             }
             if (VEC) {
-                float4 x[UNROLL][NV];
+                uint4 x[UNROLL][NV];
 #pragma unroll
                 for (int u = 0; u < UNROLL; ++u)
 #pragma unroll
                     for (int v = 0; v < NV; ++v)
-                        x[u][v] = *reinterpret_cast<const float4*>(src[u] + c4[v]);
+                        x[u][v] = *reinterpret_cast<const uint4*>(src[u] + cv[v]);
 #pragma unroll
                 for (int u = 0; u < UNROLL; ++u) {
                     const bool on = (j0 + u * S + slot) < cnt;
 #pragma unroll
                     for (int v = 0; v < NV; ++v) {
-                        acc[v][0] += on ? ww[u] * x[u][v].x : 0.f;
-                        acc[v][1] += on ? ww[u] * x[u][v].y : 0.f;
-                        acc[v][2] += on ? ww[u] * x[u][v].z : 0.f;
-                        acc[v][3] += on ? ww[u] * x[u][v].w : 0.f;
+                        float f[EPV];
+                        Elem<TIn>::unpack(x[u][v], f);
+#pragma unroll
+                        for (int i = 0; i < EPV; ++i) acc[v][i] += on ? ww[u] * f[i] : 0.f;
                     }
                 }
             } else {
@@ -179,9 +226,9 @@ __device__ inline void spmm_accumulate(const SpmmArgs& g, int64_t e_begin, int64
 #pragma unroll
                     for (int v = 0; v < NV; ++v)
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            int c = (v * G + gl) * 4 + i;
-                            if (c < g.d && ww[u] != 0.f) acc[v][i] += ww[u] * src[u][c];
+                        for (int i = 0; i < EPV; ++i) {
+                            int c = (v * G + gl) * EPV + i;
+                            if (c < g.d && ww[u] != 0.f) acc[v][i] += ww[u] * Elem<TIn>::load(src[u] + c);
                         }
             }
         }
@@ -192,46 +239,56 @@ __device__ inline void spmm_accumulate(const SpmmArgs& g, int64_t e_begin, int64
 #pragma unroll
         for (int v = 0; v < NV; ++v)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) acc[v][i] += __shfl_xor(acc[v][i], m, kWave);
+            for (int i = 0; i < EPV; ++i) acc[v][i] += __shfl_xor(acc[v][i], m, kWave);
 }
 
-template <int G, int NV, bool VEC>
-__device__ inline void spmm_store(float* o, int32_t d, int lane, float sc, const float (&acc)[NV][4])
+// Lanes 0..G-1 write sc * acc as elements of type TOut; each lane owns EPV consecutive
+// columns per vector, which is a whole 16-byte store for TOut = TIn and two for fp32 output of
+// a bf16 input.
+template <typename TOut, int EPV, int G, int NV, bool VEC>
+__device__ inline void spmm_store(TOut* o, int32_t d, int lane, float sc, const float (&acc)[NV][EPV])
 {
     if (lane >= G) return;
 #pragma unroll
     for (int v = 0; v < NV; ++v) {
-        int c4 = (v * G + lane) * 4;
+        const int c0 = (v * G + lane) * EPV;
         if (VEC) {
-            if (c4 < d)
-                *reinterpret_cast<float4*>(o + c4) =
-                    make_float4(sc * acc[v][0], sc * acc[v][1], sc * acc[v][2], sc * acc[v][3]);
+            if (c0 >= d) continue;
+            constexpr int OPV = Elem<TOut>::EPV;      // elements per 16-byte output vector
+#pragma unroll
+            for (int h = 0; h < EPV / OPV; ++h) {
+                float f[OPV];
+#pragma unroll
+                for (int i = 0; i < OPV; ++i) f[i] = sc * acc[v][h * OPV + i];
+                *reinterpret_cast<uint4*>(o + c0 + h * OPV) = Elem<TOut>::pack(f);
+            }
         } else {
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-                if (c4 + i < d) o[c4 + i] = sc * acc[v][i];
+            for (int i = 0; i < EPV; ++i)
+                if (c0 + i < d) Elem<TOut>::store(o + c0 + i, sc * acc[v][i]);
         }
     }
 }
 
-template <int G, int NV, bool VEC>
+template <typename TIn, typename TOut, int G, int NV, bool VEC>
 __global__ __launch_bounds__(kBlock) void k_spmm_items(const SpmmArgs g)
 {
+    constexpr int EPV = Elem<TIn>::EPV;
     const int lane = threadIdx.x % kWave;
     // the item index is the same for the whole wavefront; tell the compiler so that row
     // pointers and item descriptors travel through scalar registers
     const int64_t item = __builtin_amdgcn_readfirstlane(
         (int)(blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave));
-    float acc[NV][4];
+    float acc[NV][EPV];
     if (item < g.it.nsegs) {
-        // one segment of a long row -> partial sum
+        // one segment of a long row -> fp32 partial sum
 #pragma unroll
         for (int v = 0; v < NV; ++v)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) acc[v][i] = 0.f;
+            for (int i = 0; i < EPV; ++i) acc[v][i] = 0.f;
         const int64_t e0 = g.it.seg_begin[item];
-        spmm_accumulate<G, NV, VEC>(g, e0, e0 + g.it.seg_len[item], lane, acc);
-        spmm_store<G, NV, VEC>(g.partial + item * (int64_t)g.ld, g.d, lane, 1.f, acc);
+        spmm_accumulate<TIn, G, NV, VEC>(g, e0, e0 + g.it.seg_len[item], lane, acc);
+        spmm_store<float, EPV, G, NV, VEC>(g.partial + item * (int64_t)g.ld, g.d, lane, 1.f, acc);
         return;
     }
     const int64_t ri = item - g.it.nsegs;
@@ -243,19 +300,18 @@ __global__ __launch_bounds__(kBlock) void k_spmm_items(const SpmmArgs g)
 #pragma unroll
         for (int v = 0; v < NV; ++v)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) acc[v][i] = 0.f;
-        spmm_accumulate<G, NV, VEC>(g, e_begin, e_end, lane, acc);
-        spmm_store<G, NV, VEC>(g.out + row * (int64_t)g.ld, g.d, lane,
-                               g.rowscale ? g.rowscale[row] : 1.f, acc);
+            for (int i = 0; i < EPV; ++i) acc[v][i] = 0.f;
+        spmm_accumulate<TIn, G, NV, VEC>(g, e_begin, e_end, lane, acc);
+        spmm_store<TOut, EPV, G, NV, VEC>(static_cast<TOut*>(g.out) + row * (int64_t)g.ld, g.d, lane,
+                                          g.rowscale ? g.rowscale[row] : 1.f, acc);
     }
 }
 
 // out[row,:] = rowscale[row] * (partial[first,:] + partial[first+1,:] + ...): one wavefront per
-// long row and 256-float column block, segments added in ascending order (eight loads in
-// flight per lane).
-template <bool VEC>
-__global__ __launch_bounds__(kBlock) void k_spmm_long_reduce(const SpmmArgs g, int32_t c0,
-                                                             int32_t dc)
+// long row and 256-column block, segments added in ascending order (eight loads in flight per
+// lane).
+template <typename TOut, bool VEC>
+__global__ __launch_bounds__(kBlock) void k_spmm_long_reduce(const SpmmArgs g)
 {
     constexpr int U = 8;
     const int lane = threadIdx.x % kWave;
@@ -265,11 +321,11 @@ __global__ __launch_bounds__(kBlock) void k_spmm_long_reduce(const SpmmArgs g, i
     const int64_t first = g.it.long_first[i];
     const int32_t ns = g.it.long_nseg[i];
     const float sc = g.rowscale ? g.rowscale[row] : 1.f;
-    const int32_t cb = c0 + blockIdx.y * 256;          // first column of this block
-    const int32_t cend = c0 + dc;
+    const int32_t cb = blockIdx.y * 256;          // first column of this block
+    TOut* out = static_cast<TOut*>(g.out) + row * (int64_t)g.ld;
     if (VEC) {
         const int32_t c = cb + lane * 4;
-        if (c >= cend) return;
+        if (c >= g.d) return;
         float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
         for (int32_t t0 = 0; t0 < ns; t0 += U) {
             float4 x[U];
@@ -281,13 +337,15 @@ __global__ __launch_bounds__(kBlock) void k_spmm_long_reduce(const SpmmArgs g, i
 #pragma unroll
             for (int u = 0; u < U; ++u) { s.x += x[u].x; s.y += x[u].y; s.z += x[u].z; s.w += x[u].w; }
         }
-        *reinterpret_cast<float4*>(g.out + row * (int64_t)g.ld + c) =
-            make_float4(sc * s.x, sc * s.y, sc * s.z, sc * s.w);
+        Elem<TOut>::store(out + c + 0, sc * s.x);
+        Elem<TOut>::store(out + c + 1, sc * s.y);
+        Elem<TOut>::store(out + c + 2, sc * s.z);
+        Elem<TOut>::store(out + c + 3, sc * s.w);
     } else {
-        for (int32_t c = cb + lane; c < cend && c < cb + 256; c += kWave) {
+        for (int32_t c = cb + lane; c < g.d && c < cb + 256; c += kWave) {
             float s = 0.f;
             for (int32_t t = 0; t < ns; ++t) s += g.partial[(first + t) * (int64_t)g.ld + c];
-            g.out[row * (int64_t)g.ld + c] = sc * s;
+            Elem<TOut>::store(out + c, sc * s);
         }
     }
 }
@@ -342,67 +400,84 @@ void launch_scatter_rows(const void* src, const int32_t* idx, void* dst, int64_t
 }
 
 namespace {
-SpmmArgs spmm_args(const int64_t* rp, const int32_t* col, const float* w, const float* rowscale,
-                   const float* a_rows, int64_t n_a, const float* b_rows, float* out, int32_t c0,
-                   int32_t dc, int32_t d, const SpmmItems& items, float* partial)
-{
-    SpmmArgs g;
-    g.rp = rp; g.col = col; g.w = w; g.rowscale = rowscale;
-    g.a_rows = a_rows + c0; g.n_a = n_a; g.b_rows = b_rows ? b_rows + c0 : nullptr;
-    g.out = out + c0; g.d = dc; g.ld = d; g.it = items; g.partial = partial + c0;
-    return g;
-}
-}  // namespace
 
-void launch_spmm(const int64_t* rp, const int32_t* col, const float* w, const float* rowscale,
-                 const float* a_rows, int64_t n_a, const float* b_rows, float* out,
-                 int64_t nrows, int32_t d, const SpmmItems& items, float* partial, hipStream_t s)
+template <typename TIn, typename TOut>
+void spmm_typed(const int64_t* rp, const int32_t* col, const float* w, const float* rowscale,
+                const void* a_rows, int64_t n_a, const void* b_rows, void* out, int32_t d,
+                const SpmmItems& items, float* partial, hipStream_t s)
 {
-    if (nrows <= 0 || d <= 0) return;
+    constexpr int EPV = Elem<TIn>::EPV;
     const int64_t nitems = items.nsegs + items.nranges;
-    if (nitems <= 0) return;
     const int wpb = kBlock / kWave;
     const dim3 grid((unsigned)((nitems + wpb - 1) / wpb));
     const dim3 block(kBlock);
-    const bool vec = (d % 4 == 0);
-    // rows wider than 1024 floats are processed in column blocks of 1024, one launch each
-    for (int32_t c0 = 0; c0 < d; c0 += 1024) {
-        const int32_t dc = d - c0 < 1024 ? d - c0 : 1024;
-        const SpmmArgs g = spmm_args(rp, col, w, rowscale, a_rows, n_a, b_rows, out, c0, dc, d, items,
-                                     partial);
-        const int nv4 = (dc + 3) / 4;  // float4 columns of this block
+    const bool vec = (d % EPV == 0) && (d % Elem<TOut>::EPV == 0);
+    // rows wider than 256 vectors (1024 floats / 2048 bf16) are processed in column blocks
+    constexpr int32_t kColBlock = 256 * EPV;
+    for (int32_t c0 = 0; c0 < d; c0 += kColBlock) {
+        const int32_t dc = d - c0 < kColBlock ? d - c0 : kColBlock;
+        SpmmArgs g;
+        g.rp = rp; g.col = col; g.w = w; g.rowscale = rowscale;
+        g.a_rows = static_cast<const TIn*>(a_rows) + c0; g.n_a = n_a;
+        g.b_rows = b_rows ? static_cast<const TIn*>(b_rows) + c0 : nullptr;
+        g.out = static_cast<TOut*>(out) + c0; g.d = dc; g.ld = d; g.it = items;
+        g.partial = partial + c0;
+        const int nv = (dc + EPV - 1) / EPV;  // 16-byte vectors per row in this block
 #define GNN_SPMM(G, NV, VEC) \
-    hipLaunchKernelGGL((k_spmm_items<G, NV, VEC>), grid, block, 0, s, g)
+    hipLaunchKernelGGL((k_spmm_items<TIn, TOut, G, NV, VEC>), grid, block, 0, s, g)
         if (vec) {
-            if (nv4 <= 8) GNN_SPMM(8, 1, true);
-            else if (nv4 <= 16) GNN_SPMM(16, 1, true);
-            else if (nv4 <= 32) GNN_SPMM(32, 1, true);
-            else if (nv4 <= 64) GNN_SPMM(64, 1, true);
-            else if (nv4 <= 128) GNN_SPMM(64, 2, true);
+            if (nv <= 8) GNN_SPMM(8, 1, true);
+            else if (nv <= 16) GNN_SPMM(16, 1, true);
+            else if (nv <= 32) GNN_SPMM(32, 1, true);
+            else if (nv <= 64) GNN_SPMM(64, 1, true);
+            else if (nv <= 128) GNN_SPMM(64, 2, true);
             else GNN_SPMM(64, 4, true);
         } else {
-            if (nv4 <= 8) GNN_SPMM(8, 1, false);
-            else if (nv4 <= 16) GNN_SPMM(16, 1, false);
-            else if (nv4 <= 32) GNN_SPMM(32, 1, false);
-            else if (nv4 <= 64) GNN_SPMM(64, 1, false);
-            else if (nv4 <= 128) GNN_SPMM(64, 2, false);
+            if (nv <= 8) GNN_SPMM(8, 1, false);
+            else if (nv <= 16) GNN_SPMM(16, 1, false);
+            else if (nv <= 32) GNN_SPMM(32, 1, false);
+            else if (nv <= 64) GNN_SPMM(64, 1, false);
+            else if (nv <= 128) GNN_SPMM(64, 2, false);
             else GNN_SPMM(64, 4, false);
         }
 #undef GNN_SPMM
     }
 }
 
-void launch_spmm_reduce(const float* rowscale, float* out, int32_t d, const SpmmItems& items,
-                        float* partial, hipStream_t s)
+template <typename TOut>
+void spmm_reduce_typed(const float* rowscale, void* out, int32_t d, const SpmmItems& items,
+                       float* partial, hipStream_t s)
+{
+    const int wpb = kBlock / kWave;
+    SpmmArgs g{};
+    g.rowscale = rowscale; g.out = out; g.d = d; g.ld = d; g.it = items; g.partial = partial;
+    const dim3 rgrid((unsigned)((items.nlong + wpb - 1) / wpb), (unsigned)((d + 255) / 256));
+    if (d % 4 == 0) hipLaunchKernelGGL((k_spmm_long_reduce<TOut, true>), rgrid, dim3(kBlock), 0, s, g);
+    else hipLaunchKernelGGL((k_spmm_long_reduce<TOut, false>), rgrid, dim3(kBlock), 0, s, g);
+}
+
+}  // namespace
+
+void launch_spmm(const int64_t* rp, const int32_t* col, const float* w, const float* rowscale,
+                 const void* a_rows, int64_t n_a, const void* b_rows, void* out, int64_t nrows,
+                 int32_t d, int in_bf16, int out_bf16, const SpmmItems& items, float* partial,
+                 hipStream_t s)
+{
+    if (nrows <= 0 || d <= 0 || items.nsegs + items.nranges <= 0) return;
+    if (!in_bf16)
+        spmm_typed<float, float>(rp, col, w, rowscale, a_rows, n_a, b_rows, out, d, items, partial, s);
+    else if (out_bf16)
+        spmm_typed<uint16_t, uint16_t>(rp, col, w, rowscale, a_rows, n_a, b_rows, out, d, items, partial, s);
+    else
+        spmm_typed<uint16_t, float>(rp, col, w, rowscale, a_rows, n_a, b_rows, out, d, items, partial, s);
+}
+
+void launch_spmm_reduce(const float* rowscale, void* out, int32_t d, int out_bf16,
+                        const SpmmItems& items, float* partial, hipStream_t s)
 {
     if (items.nlong <= 0 || d <= 0) return;
-    const int wpb = kBlock / kWave;
-    const bool vec = (d % 4 == 0);
-    SpmmArgs g = spmm_args(nullptr, nullptr, nullptr, rowscale, nullptr, 0, nullptr, out, 0, d, d, items,
-                           partial);
-    const dim3 rgrid((unsigned)((items.nlong + wpb - 1) / wpb), (unsigned)((d + 255) / 256));
-    if (vec) hipLaunchKernelGGL(k_spmm_long_reduce<true>, rgrid, dim3(kBlock), 0, s, g, 0, d);
-    else hipLaunchKernelGGL(k_spmm_long_reduce<false>, rgrid, dim3(kBlock), 0, s, g, 0, d);
+    if (out_bf16) spmm_reduce_typed<uint16_t>(rowscale, out, d, items, partial, s);
+    else spmm_reduce_typed<float>(rowscale, out, d, items, partial, s);
 }
 
 void launch_scatter_add(const float* src, int64_t nrows, int64_t n_own, int64_t base_row,

@@ -56,3 +56,41 @@ def random_weights(dims, seed, sage, bias=True):
             "b": 0.1 * rng.standard_normal(dims[l + 1]) if bias else None,
         })
     return out
+
+
+def aligned_backward(og, fwd, got_act, weights, X, labels, mask, tol, say=None):
+    """Oracle backward with the activation decisions of the other implementation on the
+    elements where the two disagree, after checking that each disagreement is legitimate:
+    the oracle's pre-activation and the other side's activation both lie within
+    ``tol * max|A^l|`` of zero, i.e. inside the forward tolerance band, where either decision
+    is a correct result.  Returns the oracle's backward dict (plus ``act``)."""
+    relu_on = []
+    L = fwd.L
+    for l in range(L - 1):
+        on_got = np.asarray(got_act[l]) > 0
+        on_ref = fwd.act[l] > 0
+        diff = np.argwhere(on_got != on_ref)
+        band = tol * np.abs(fwd.act[l]).max()
+        prev = np.asarray(X, dtype=np.float64) if l == 0 else fwd.act[l - 1]
+        W = np.asarray(weights[l]["W"], dtype=np.float64)
+        Ws = weights[l].get("Ws")
+        b = weights[l].get("b")
+        if len(diff):
+            v, c = diff[:, 0], diff[:, 1]
+            pre = np.einsum("ij,ji->i", fwd.z[l][v], W[:, c])
+            if Ws is not None and fwd.m == 1:
+                pre = pre + np.einsum("ij,ji->i", prev[v], np.asarray(Ws, dtype=np.float64)[:, c])
+            if b is not None:
+                pre = pre + np.asarray(b, dtype=np.float64)[c]
+            assert np.abs(pre).max() <= band, (l, float(np.abs(pre).max()), band)
+            assert np.abs(np.asarray(got_act[l])[v, c]).max() <= band
+        if say:
+            say("layer %d: %d of %d activation decisions differ, all within +-%.2g of zero"
+                % (l + 1, len(diff), on_ref.size, band))
+        on = on_ref.astype(np.uint8)
+        if len(diff):
+            on[diff[:, 0], diff[:, 1]] = on_got[diff[:, 0], diff[:, 1]]
+        relu_on.append(on)
+    out = og.backward(fwd, labels, mask, relu_on=relu_on)
+    out["act"] = fwd.act
+    return out

@@ -9,7 +9,7 @@ import time
 import numpy as np
 import pytest
 
-from helpers import rel_err
+from helpers import aligned_backward, rel_err
 
 pytestmark = pytest.mark.gpu
 TOL = 1e-4
@@ -70,29 +70,9 @@ def test_mid_workload_full_size(capsys):
         assert rel_err(a, b) <= TOL, ("act", l)
 
     # The backward pass branches on A^l > 0.  Where a pre-activation lies within rounding
-    # distance of zero the two sides may legitimately decide differently, and either decision
-    # is a correct result.  Check that every disagreement is of that kind (both values inside
-    # the forward tolerance band around zero), then let the oracle's backward take the same
-    # decision on exactly those elements so that the rest can be compared one to one.
-    relu_on = []
-    for l in range(len(dims) - 2):
-        on_gpu = got["act"][l] > 0
-        on_ref = fwd.act[l] > 0
-        diff = np.argwhere(on_gpu != on_ref)
-        band = TOL * np.abs(fwd.act[l]).max()
-        prev = X if l == 0 else fwd.act[l - 1]
-        for v, c in diff:
-            pre = fwd.z[l][v] @ w[l]["W"][:, c].astype(np.float64) + \
-                prev[v].astype(np.float64) @ w[l]["Ws"][:, c].astype(np.float64) + float(w[l]["b"][c])
-            assert abs(pre) <= band and abs(float(got["act"][l][v, c])) <= band, (l, v, c, pre)
-        say("layer %d: %d of %d activation decisions differ, all within +-%.2g of zero"
-            % (l + 1, len(diff), on_ref.size, band))
-        on = on_ref.astype(np.uint8)
-        on[tuple(diff.T)] = on_gpu[tuple(diff.T)]
-        relu_on.append(on)
-        del on_gpu, on_ref
-    ref = og.backward(fwd, y, m, relu_on=relu_on)
-    ref["act"] = fwd.act
+    # distance of zero the two sides may legitimately decide differently; the helper checks
+    # that every disagreement is of that kind and lets the oracle take the same decision there.
+    ref = aligned_backward(og, fwd, got["act"], w, X, y, m, TOL, say)
     say("oracle epoch done, loss %.6f" % ref["loss"])
     assert abs(loss - ref["loss"]) <= TOL * abs(ref["loss"])
     worst = {}

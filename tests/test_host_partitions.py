@@ -132,8 +132,5 @@ def test_argument_errors_are_reported():
 
 def test_unsupported_requests_say_so():
     with pytest.raises(GnnError) as e:
-        Context("gcn", (4, 3), dtype=1)                           # bf16 storage
-    assert e.value.status == 5
-    with pytest.raises(GnnError) as e:
         Context("gcn", (4, 3), hbm_budget_bytes=1 << 20)          # streaming schedule
     assert e.value.status == 5
