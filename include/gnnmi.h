@@ -57,7 +57,9 @@ typedef struct {
     int32_t n_layers;         /* L >= 1 */
     const int32_t *dims;      /* host, L+1 entries d_0..d_L, each >= 1 (copied) */
     int32_t has_bias;         /* 0 or 1 */
-    int64_t hbm_budget_bytes; /* 0 = everything resident in HBM */
+    int64_t hbm_budget_bytes; /* 0 = everything resident in HBM; > 0 = streaming schedule: bytes of
+                               * device memory the library may allocate for its partition-block
+                               * caches (see gnn_bind) */
 } gnn_config;
 
 /* Sizes the caller needs to allocate buffers and to account traffic. */
@@ -150,8 +152,20 @@ gnn_status gnn_workspace_bytes(const gnn_ctx *ctx, int64_t *staging, int64_t *sc
  *   labels [n] int32 in [0, d_L);  train_mask [n] uint8
  *   staging, scratch: at least gnn_workspace_bytes(), 256-byte aligned
  * The pointer arrays themselves are host memory and are copied.
+ *
+ * Streaming schedule (hbm_budget_bytes > 0; the one-GPU analogue of the paper's partition-wise
+ * cache with copy/compute overlap): feat, act[] and grad_act[] are PINNED HOST buffers of the
+ * same shapes and order; everything else stays device memory.  The library then allocates
+ * hbm_budget_bytes of device memory as a cache of partition blocks (layer l-1 activations,
+ * least-recently-used eviction; gradient blocks of layer l-1 as a write-back cache) plus six
+ * transfer buffers of max n_p x max d_l x 4 bytes and two side streams, all freed by
+ * gnn_destroy or the next gnn_build_partitions.  Only gnn_epoch runs in this mode (the
+ * per-partition entry points return GNN_EUNSUPPORTED), at most 4096 partitions, and the budget
+ * must hold two activation blocks and two gradient blocks of the widest layer (GNN_ENOMEM
+ * otherwise).  Results are bit-identical to the resident schedule.
+ *
  * Errors: GNN_ESTATE before gnn_build_partitions, GNN_EINVAL on a null entry,
- * GNN_EHIP / GNN_ENOMEM if the upload fails. */
+ * GNN_EHIP / GNN_ENOMEM if the upload or an allocation fails. */
 gnn_status gnn_bind(gnn_ctx *ctx, const void *feat, void *const *act, void *const *grad_act,
                     const void *const *weights, void *const *grad_w, const int32_t *labels,
                     const uint8_t *train_mask, void *staging, void *scratch);

@@ -221,7 +221,8 @@ class Session:
     them.  Results are read back in original vertex order."""
 
     def __init__(self, model, dims, rowptr, colidx, k, part_mode, seed, X, weights, labels,
-                 train_mask, has_bias=True, user_part=None, device="cuda:0", dtype="f32"):
+                 train_mask, has_bias=True, user_part=None, device="cuda:0", dtype="f32",
+                 hbm_budget_bytes=0):
         import torch
         self.torch = torch
         if not torch.cuda.is_available():
@@ -229,7 +230,11 @@ class Session:
         self.dev = torch.device(device)
         self.bf16 = dtype in ("bf16", GNN_BF16)
         store = torch.bfloat16 if self.bf16 else torch.float32
-        self.ctx = Context(model, dims, dtype=GNN_BF16 if self.bf16 else GNN_F32, has_bias=has_bias)
+        # hbm_budget_bytes != 0: streaming schedule; features, activations and their gradients
+        # then live in pinned host memory and the library caches partition blocks in HBM
+        self.streaming = hbm_budget_bytes != 0
+        self.ctx = Context(model, dims, dtype=GNN_BF16 if self.bf16 else GNN_F32, has_bias=has_bias,
+                           hbm_budget_bytes=hbm_budget_bytes)
         self.ctx.build_partitions(rowptr, colidx, k, part_mode, seed, user_part)
         self.model = _MODEL.get(model, model)
         self.dims = list(dims)
@@ -240,15 +245,20 @@ class Session:
         stream = self.stream
         # inputs: upload in original order, permute on the device
         # bf16 storage: values are converted once here (round to nearest even)
-        self.feat = self._to_library(
-            t.from_numpy(np.ascontiguousarray(X, dtype=np.float32)).to(store))
         self.labels = self._to_library(t.from_numpy(np.ascontiguousarray(labels, dtype=np.int32)))
         self.mask = self._to_library(t.from_numpy(np.ascontiguousarray(train_mask, dtype=np.uint8)))
-        self.act = [t.zeros((self.n, dims[l + 1]), device=self.dev,
-                            dtype=store if l < self.L - 1 else t.float32)   # logits stay fp32
-                    for l in range(self.L)]
-        self.gact = [t.zeros((self.n, dims[l + 1]), dtype=t.float32, device=self.dev)
-                     for l in range(self.L)]
+        if self.streaming:
+            self.order = t.from_numpy(self.ctx.get_order()[0].astype(np.int64))
+            big = dict(device="cpu", pin_memory=True)
+            self.feat = t.from_numpy(np.ascontiguousarray(X, dtype=np.float32)).to(store)[self.order] \
+                .contiguous().pin_memory()
+        else:
+            big = dict(device=self.dev)
+            self.feat = self._to_library(
+                t.from_numpy(np.ascontiguousarray(X, dtype=np.float32)).to(store))
+        self.act = [t.zeros((self.n, dims[l + 1]), dtype=store if l < self.L - 1 else t.float32, **big)
+                    for l in range(self.L)]                                  # logits stay fp32
+        self.gact = [t.zeros((self.n, dims[l + 1]), dtype=t.float32, **big) for l in range(self.L)]
         self.w, self.gw = [], []
         for l in range(self.L):
             for key in ("W", "Ws", "b"):
@@ -288,8 +298,12 @@ class Session:
         return dst
 
     def to_original(self, dev_tensor):
-        """Device tensor in library order -> numpy array in original vertex order."""
+        """Tensor in library order -> numpy array in original vertex order."""
         t = self.torch
+        if not dev_tensor.is_cuda:
+            out = t.empty_like(dev_tensor, pin_memory=False)
+            out[self.order] = dev_tensor
+            return out.float().numpy()
         dst = t.empty_like(dev_tensor)
         row_bytes = dev_tensor.element_size() * (dev_tensor.shape[1] if dev_tensor.dim() == 2 else 1)
         self.ctx.permute_rows(dev_tensor.data_ptr(), dst.data_ptr(), row_bytes, False, self.stream)

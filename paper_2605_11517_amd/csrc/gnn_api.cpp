@@ -6,7 +6,7 @@
 #include <cstring>
 #include <new>
 
-#include "gnn_internal.h"
+#include "gnn_ctx.h"
 
 using namespace gnnmi;
 
@@ -17,81 +17,7 @@ thread_local std::string g_create_error;
 constexpr int64_t kAlign = 256;
 int64_t align_up(int64_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
-struct DevMeta {
-    int64_t* rp = nullptr;
-    int32_t* lcol = nullptr;
-    float* ew = nullptr;
-    float* rscale = nullptr;
-    int32_t* bnd = nullptr;
-    int64_t* trp = nullptr;
-    int32_t* tcol = nullptr;
-    float* tw = nullptr;
-    int32_t* order = nullptr;
-    struct Plan {
-        int32_t* range_rows = nullptr;
-        int32_t* seg_row = nullptr;
-        int64_t* seg_begin = nullptr;
-        int32_t* seg_len = nullptr;
-        int32_t* long_row = nullptr;
-        int32_t* long_first = nullptr;
-        int32_t* long_nseg = nullptr;
-    } fwd, bwd;
-    bool ready = false;
-};
-
-struct Workspace {  // byte offsets into `scratch`
-    int64_t z = 0, dy = 0, dz = 0, dga = 0, partial = 0, colpart = 0, losspart = 0, scalars = 0, segpart = 0;
-    int64_t staging_bytes = 0, scratch_bytes = 0;
-};
-
 }  // namespace
-
-struct gnn_ctx {
-    int32_t model = 0, dtype = 0, L = 0, has_bias = 1;
-    int64_t hbm_budget = 0;
-    std::vector<int32_t> dims;
-    mutable std::string err;
-    bool built = false, bound = false;
-    HostMeta M;
-    DevMeta D;
-    Workspace ws;
-    // bound buffers
-    const char* feat = nullptr;          // dtype of the context
-    std::vector<char*> act;              // act[l-1]: dtype for l < L, fp32 for l = L
-    std::vector<float*> gact;
-    std::vector<const char*> w;          // W, W_s: dtype; b: fp32
-    std::vector<float*> gw;
-    const int32_t* labels = nullptr;
-    const uint8_t* mask = nullptr;
-    char* staging = nullptr;
-    char* scratch = nullptr;
-    // schedule state
-    int32_t staged_layer = -1, staged_p = -1;
-    std::vector<uint8_t> fwd_done;      // L * k
-    std::vector<int32_t> bwd_done;      // per layer: partitions finished since gnn_loss
-    bool loss_done = false;
-    // profiling
-    bool prof = false;
-    std::vector<hipEvent_t> events;
-    std::vector<int> event_class;
-    size_t events_used = 0;
-    double prof_ms[GNN_K_COUNT] = {0};
-    int64_t prof_launches[GNN_K_COUNT] = {0};
-
-    gnn_status fail(gnn_status st, const std::string& msg) const
-    {
-        err = msg;
-        return st;
-    }
-    bool bf16() const { return dtype == GNN_BF16; }
-    int64_t es() const { return dtype == GNN_BF16 ? 2 : 4; }   // bytes per stored activation/weight
-    // rows [r0, ...) of the input of `layer` (A^{layer-1}), width d
-    const char* layer_input(int32_t layer, int64_t r0 = 0) const
-    {
-        const char* base = layer == 1 ? feat : act[(size_t)layer - 2];
-        return base + r0 * (int64_t)dims[(size_t)layer - 1] * es();
-    }
-};
 
 namespace {
 
@@ -102,6 +28,7 @@ void free_device(DevMeta& D)
     if (D.ew) (void)hipFree(D.ew);
     if (D.rscale) (void)hipFree(D.rscale);
     if (D.bnd) (void)hipFree(D.bnd);
+    if (D.bnd_local) (void)hipFree(D.bnd_local);
     if (D.trp) (void)hipFree(D.trp);
     if (D.tcol) (void)hipFree(D.tcol);
     if (D.tw) (void)hipFree(D.tw);
@@ -140,6 +67,7 @@ gnn_status ensure_device(gnn_ctx* c)
     step(upload(D.ew, M.ew));
     step(upload(D.rscale, M.rscale));
     step(upload(D.bnd, M.bnd));
+    step(upload(D.bnd_local, M.bnd_local));
     step(upload(D.trp, M.trp));
     step(upload(D.tcol, M.tcol));
     step(upload(D.tw, M.tw));
@@ -189,60 +117,10 @@ void compute_workspace(gnn_ctx* c)
     w.dga = take(max_r * din);
     w.partial = take(part);
     w.colpart = take(act_bwd_partial_floats(max_np, (int32_t)dout));
-    w.losspart = take(loss_partial_floats(M.n));
+    w.losspart = take(loss_partial_floats(M.n, M.k));
     w.scalars = take(64);
     w.segpart = take(std::max(M.plan_fwd.max_segs, M.plan_bwd.max_segs) * din);
     w.scratch_bytes = o;
-}
-
-// ---- profiling brackets ---------------------------------------------------------------------
-struct Timed {
-    gnn_ctx* c;
-    hipStream_t s;
-    Timed(gnn_ctx* ctx, hipStream_t st, int cls) : c(ctx), s(st)
-    {
-        if (!c->prof) return;
-        mark(cls);
-    }
-    ~Timed()
-    {
-        if (!c->prof) return;
-        mark(-1);
-    }
-    void mark(int cls)
-    {
-        if (c->events_used == c->events.size()) {
-            hipEvent_t e;
-            if (hipEventCreate(&e) != hipSuccess) return;
-            c->events.push_back(e);
-            c->event_class.push_back(0);
-        }
-        c->event_class[c->events_used] = cls;
-        (void)hipEventRecord(c->events[c->events_used], s);
-        ++c->events_used;
-    }
-};
-
-void collect_profile(gnn_ctx* c)
-{
-    for (int i = 0; i < GNN_K_COUNT; ++i) { c->prof_ms[i] = 0; c->prof_launches[i] = 0; }
-    for (size_t i = 0; i + 1 < c->events_used; i += 2) {
-        int cls = c->event_class[i];
-        float ms = 0.f;
-        if (cls >= 0 && cls < GNN_K_COUNT &&
-            hipEventElapsedTime(&ms, c->events[i], c->events[i + 1]) == hipSuccess) {
-            c->prof_ms[cls] += ms;
-            c->prof_launches[cls] += 1;
-        }
-    }
-    c->events_used = 0;
-}
-
-gnn_status check_launch(gnn_ctx* c, const char* what)
-{
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return c->fail(GNN_EHIP, std::string(what) + ": " + hipGetErrorString(e));
-    return GNN_OK;
 }
 
 gnn_status check_lp(gnn_ctx* c, int32_t layer, int32_t p)
@@ -250,6 +128,10 @@ gnn_status check_lp(gnn_ctx* c, int32_t layer, int32_t p)
     if (!c->bound) return c->fail(GNN_ESTATE, "buffers are not bound (call gnn_bind)");
     if (layer < 1 || layer > c->L) return c->fail(GNN_EINVAL, "layer outside 1..L");
     if (p < 0 || p >= c->M.k) return c->fail(GNN_EINVAL, "partition outside 0..k-1");
+    if (c->streaming())
+        return c->fail(GNN_EUNSUPPORTED,
+                       "with a streaming budget only gnn_epoch drives the schedule; the per-partition "
+                       "entry points need resident buffers");
     return GNN_OK;
 }
 
@@ -271,8 +153,8 @@ SpmmItems plan_items(const HostMeta::Plan& H, const DevMeta::Plan& P, int32_t p)
     return it;
 }
 
-// Z_p = S_p [own rows ; staging]
-void run_spmm_fwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
+// Z_p = S_p [in_own ; staging]
+void run_spmm_fwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, hipStream_t s)
 {
     const HostMeta& M = c->M;
     const int64_t r0 = M.off[(size_t)p], np = M.off[(size_t)p + 1] - r0;
@@ -284,8 +166,8 @@ void run_spmm_fwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
     const int b16 = c->bf16() ? 1 : 0;
     {
         Timed t(c, s, GNN_K_SPMM);
-        launch_spmm(c->D.rp + r0, c->D.lcol, c->D.ew, rscale, c->layer_input(layer, r0), np,
-                    c->staging, Z, np, din, b16, b16, items, segpart, s);
+        launch_spmm(c->D.rp + r0, c->D.lcol, c->D.ew, rscale, in_own, np, c->staging, Z, np, din, b16,
+                    b16, items, segpart, s);
     }
     if (items.nlong > 0) {
         Timed t(c, s, GNN_K_SPMM_REDUCE);
@@ -294,6 +176,156 @@ void run_spmm_fwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
 }
 
 }  // namespace
+
+namespace gnnmi {
+
+void collect_profile(gnn_ctx* c)
+{
+    for (int i = 0; i < GNN_K_COUNT; ++i) { c->prof_ms[i] = 0; c->prof_launches[i] = 0; }
+    for (size_t i = 0; i + 1 < c->events_used; i += 2) {
+        int cls = c->event_class[i];
+        float ms = 0.f;
+        if (cls >= 0 && cls < GNN_K_COUNT &&
+            hipEventElapsedTime(&ms, c->events[i], c->events[i + 1]) == hipSuccess) {
+            c->prof_ms[cls] += ms;
+            c->prof_launches[cls] += 1;
+        }
+    }
+    c->events_used = 0;
+}
+
+void zero_weight_grads(gnn_ctx* c, hipStream_t s)
+{
+    Timed t(c, s, GNN_K_OTHER);
+    for (int32_t l = 0; l < c->L; ++l) {
+        const int64_t wsz = (int64_t)c->dims[(size_t)l] * c->dims[(size_t)l + 1] * 4;
+        launch_fill_zero(c->gw[(size_t)3 * l], wsz, s);
+        if (c->model == GNN_SAGE_MEAN) launch_fill_zero(c->gw[(size_t)3 * l + 1], wsz, s);
+        if (c->has_bias) launch_fill_zero(c->gw[(size_t)3 * l + 2], (int64_t)c->dims[(size_t)l + 1] * 4, s);
+    }
+}
+
+void compute_fwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, char* out_own, hipStream_t s)
+{
+    const HostMeta& M = c->M;
+    const int64_t np = M.off[(size_t)p + 1] - M.off[(size_t)p];
+    const int32_t din = c->dims[(size_t)layer - 1], dout = c->dims[(size_t)layer];
+    run_spmm_fwd(c, layer, p, in_own, s);
+    Timed t(c, s, GNN_K_GEMM_FWD);
+    GemmEpilogue ep;
+    ep.bias = c->has_bias ? (const float*)c->w[(size_t)3 * (layer - 1) + 2] : nullptr;
+    ep.relu = layer < c->L ? 1 : 0;
+    const bool sage = c->model == GNN_SAGE_MEAN;
+    if (!c->bf16()) {
+        GemmSeg seg[2];
+        seg[0].a = (const float*)(c->scratch + c->ws.z); seg[0].lda = din;
+        seg[0].b = (const float*)c->w[(size_t)3 * (layer - 1)]; seg[0].ldb = dout; seg[0].k = din;
+        if (sage) {
+            seg[1].a = (const float*)in_own; seg[1].lda = din;
+            seg[1].b = (const float*)c->w[(size_t)3 * (layer - 1) + 1]; seg[1].ldb = dout; seg[1].k = din;
+        }
+        launch_gemm_nn(seg, sage ? 2 : 1, (float*)out_own, dout, np, dout, ep, s);
+    } else {
+        GemmSegBf16 seg[2];
+        seg[0].a = c->scratch + c->ws.z; seg[0].lda = din;
+        seg[0].b = c->w[(size_t)3 * (layer - 1)]; seg[0].ldb = dout; seg[0].k = din;
+        if (sage) {
+            seg[1].a = in_own; seg[1].lda = din;
+            seg[1].b = c->w[(size_t)3 * (layer - 1) + 1]; seg[1].ldb = dout; seg[1].k = din;
+        }
+        launch_gemm_bf16_nn(seg, sage ? 2 : 1, out_own, layer < c->L ? 1 : 0 /* logits stay fp32 */, dout,
+                            np, dout, ep, s);
+    }
+}
+
+const char* compute_bwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, const float* g_own,
+                        const char* act_own, hipStream_t s)
+{
+    const HostMeta& M = c->M;
+    const int32_t L = c->L;
+    const int64_t np = M.off[(size_t)p + 1] - M.off[(size_t)p];
+    const int64_t nb = M.boff[(size_t)p + 1] - M.boff[(size_t)p];
+    const int32_t din = c->dims[(size_t)layer - 1], dout = c->dims[(size_t)layer];
+    const char* W = c->w[(size_t)3 * (layer - 1)];
+    float* gW = c->gw[(size_t)3 * (layer - 1)];
+    float* gWs = c->gw[(size_t)3 * (layer - 1) + 1];
+    float* gb = c->has_bias ? c->gw[(size_t)3 * (layer - 1) + 2] : nullptr;
+    char* Z = c->scratch + c->ws.z;
+    char* dYbuf = c->scratch + c->ws.dy;
+    char* dZ = c->scratch + c->ws.dz;
+    float* dGA = (float*)(c->scratch + c->ws.dga);
+    float* partial = (float*)(c->scratch + c->ws.partial);
+    float* colpart = (float*)(c->scratch + c->ws.colpart);
+    const bool b16 = c->bf16();
+    const bool sage = c->model == GNN_SAGE_MEAN;
+
+    // activation backward: dY = grad A ⊙ [A > 0] on hidden layers, grad A itself on the last
+    const char* dY = (const char*)g_own;
+    {
+        Timed t(c, s, GNN_K_ACT_BWD);
+        if (b16) {
+            launch_act_bwd_bf16(g_own, layer < L ? act_own : nullptr, dYbuf, np, dout, gb, colpart, s);
+            dY = dYbuf;
+        } else if (layer < L) {
+            launch_act_bwd(g_own, (const float*)act_own, (float*)dYbuf, np, dout, gb, colpart, s);
+            dY = dYbuf;
+        } else {
+            launch_act_bwd(g_own, nullptr, nullptr, np, dout, gb, colpart, s);
+        }
+    }
+    // recompute the aggregate from the regathered rows
+    run_spmm_fwd(c, layer, p, in_own, s);
+    // weight gradients, summed over partitions
+    {
+        Timed t(c, s, GNN_K_GEMM_DW);
+        if (b16) {
+            launch_gemm_bf16_tn(Z, din, dY, dout, gW, dout, din, dout, np, partial, s);
+            if (sage) launch_gemm_bf16_tn(in_own, din, dY, dout, gWs, dout, din, dout, np, partial, s);
+        } else {
+            launch_gemm_tn((const float*)Z, din, (const float*)dY, dout, gW, dout, din, dout, np, partial, s);
+            if (sage)
+                launch_gemm_tn((const float*)in_own, din, (const float*)dY, dout, gWs, dout, din, dout, np,
+                               partial, s);
+        }
+    }
+    if (layer >= 2) {
+        {
+            Timed t(c, s, GNN_K_GEMM_DZ);
+            GemmEpilogue ep;
+            if (b16) launch_gemm_bf16_nt(dY, dout, W, dout, dZ, 1, din, np, din, dout, ep, s);
+            else launch_gemm_nt((const float*)dY, dout, (const float*)W, dout, (float*)dZ, din, np, din, dout, ep, s);
+        }
+        const int64_t t0 = M.toff[(size_t)p];
+        const SpmmItems items = plan_items(M.plan_bwd, c->D.bwd, p);
+        float* segpart = (float*)(c->scratch + c->ws.segpart);
+        {
+            Timed t(c, s, GNN_K_SPMM_T);
+            launch_spmm(c->D.trp + t0, c->D.tcol, c->D.tw, nullptr, dZ, np, nullptr, dGA, np + nb, din,
+                        b16 ? 1 : 0, 0, items, segpart, s);
+        }
+        if (items.nlong > 0) {
+            Timed t(c, s, GNN_K_SPMM_REDUCE);
+            launch_spmm_reduce(nullptr, dGA, din, 0, items, segpart, s);
+        }
+    }
+    return dY;
+}
+
+void compute_bwd_self(gnn_ctx* c, int32_t layer, int32_t p, const char* dY, float* gprev_own,
+                      hipStream_t s)
+{
+    if (c->model != GNN_SAGE_MEAN || layer < 2) return;
+    const int64_t np = c->M.off[(size_t)p + 1] - c->M.off[(size_t)p];
+    const int32_t din = c->dims[(size_t)layer - 1], dout = c->dims[(size_t)layer];
+    const char* Ws = c->w[(size_t)3 * (layer - 1) + 1];
+    Timed t(c, s, GNN_K_GEMM_DZ);
+    GemmEpilogue ep;
+    ep.accumulate = 1;
+    if (c->bf16()) launch_gemm_bf16_nt(dY, dout, Ws, dout, gprev_own, 0, din, np, din, dout, ep, s);
+    else launch_gemm_nt((const float*)dY, dout, (const float*)Ws, dout, gprev_own, din, np, din, dout, ep, s);
+}
+
+}  // namespace gnnmi
 
 // =================================================================================================
 extern "C" {
@@ -311,8 +343,6 @@ gnn_status gnn_create(const gnn_config* cfg, gnn_ctx** out)
         if (cfg->dims[l] < 1 || cfg->dims[l] > (1 << 20)) return bad(GNN_EINVAL, "layer width out of range");
     if (cfg->has_bias != 0 && cfg->has_bias != 1) return bad(GNN_EINVAL, "has_bias must be 0 or 1");
     if (cfg->hbm_budget_bytes < 0) return bad(GNN_EINVAL, "hbm_budget_bytes must be >= 0");
-    if (cfg->hbm_budget_bytes != 0)
-        return bad(GNN_EUNSUPPORTED, "streaming from pinned host memory is not implemented yet");
     gnn_ctx* c = new (std::nothrow) gnn_ctx();
     if (!c) return bad(GNN_ENOMEM, "out of host memory");
     c->model = cfg->model;
@@ -328,6 +358,7 @@ gnn_status gnn_create(const gnn_config* cfg, gnn_ctx** out)
 void gnn_destroy(gnn_ctx* c)
 {
     if (!c) return;
+    stream_engine_destroy(c);
     if (c->D.ready) free_device(c->D);
     for (hipEvent_t e : c->events) (void)hipEventDestroy(e);
     delete c;
@@ -339,12 +370,15 @@ gnn_status gnn_build_partitions(gnn_ctx* c, int64_t n, const int64_t* rowptr, co
                                 int32_t k, int32_t mode, uint64_t seed, const int32_t* user_part)
 {
     if (!c) return GNN_EINVAL;
+    if (c->streaming() && k > 4096)
+        return c->fail(GNN_EINVAL, "the streaming schedule supports at most 4096 partitions");
     gnn_status st;
     try {
         HostMeta M;
         std::string err;
-        st = build_host_meta(c->model, n, rowptr, colidx, k, mode, seed, user_part, M, err);
+        st = build_host_meta(c->model, n, rowptr, colidx, k, mode, seed, user_part, c->streaming(), M, err);
         if (st != GNN_OK) return c->fail(st, err);
+        stream_engine_destroy(c);
         if (c->D.ready) free_device(c->D);
         c->M = std::move(M);
     } catch (const std::bad_alloc&) {
@@ -447,11 +481,15 @@ gnn_status gnn_bind(gnn_ctx* c, const void* feat, void* const* act, void* const*
     c->mask = train_mask;
     c->staging = (char*)staging;
     c->scratch = (char*)scratch;
-    c->bound = true;
     c->staged_layer = c->staged_p = -1;
     c->loss_done = false;
     std::fill(c->fwd_done.begin(), c->fwd_done.end(), 0);
     std::fill(c->bwd_done.begin(), c->bwd_done.end(), 0);
+    if (c->streaming()) {
+        st = stream_engine_create(c);
+        if (st != GNN_OK) return st;
+    }
+    c->bound = true;
     return GNN_OK;
 }
 
@@ -495,40 +533,11 @@ gnn_status gnn_layer_fwd(gnn_ctx* c, int32_t layer, int32_t p, void* stream)
     if (c->staged_layer != layer || c->staged_p != p)
         return c->fail(GNN_ESTATE, "staging does not hold this (layer, partition); call gnn_gather_boundary first");
     hipStream_t s = (hipStream_t)stream;
-    const HostMeta& M = c->M;
-    const int64_t r0 = M.off[(size_t)p], np = M.off[(size_t)p + 1] - r0;
-    const int32_t din = c->dims[(size_t)layer - 1], dout = c->dims[(size_t)layer];
-    run_spmm_fwd(c, layer, p, s);
-    {
-        Timed t(c, s, GNN_K_GEMM_FWD);
-        GemmEpilogue ep;
-        ep.bias = c->has_bias ? (const float*)c->w[(size_t)3 * (layer - 1) + 2] : nullptr;
-        ep.relu = layer < c->L ? 1 : 0;
-        const bool sage = c->model == GNN_SAGE_MEAN;
-        if (!c->bf16()) {
-            GemmSeg seg[2];
-            seg[0].a = (const float*)(c->scratch + c->ws.z); seg[0].lda = din;
-            seg[0].b = (const float*)c->w[(size_t)3 * (layer - 1)]; seg[0].ldb = dout; seg[0].k = din;
-            if (sage) {
-                seg[1].a = (const float*)c->layer_input(layer, r0); seg[1].lda = din;
-                seg[1].b = (const float*)c->w[(size_t)3 * (layer - 1) + 1]; seg[1].ldb = dout; seg[1].k = din;
-            }
-            launch_gemm_nn(seg, sage ? 2 : 1, (float*)c->act[(size_t)layer - 1] + r0 * dout, dout, np,
-                           dout, ep, s);
-        } else {
-            GemmSegBf16 seg[2];
-            seg[0].a = c->scratch + c->ws.z; seg[0].lda = din;
-            seg[0].b = c->w[(size_t)3 * (layer - 1)]; seg[0].ldb = dout; seg[0].k = din;
-            if (sage) {
-                seg[1].a = c->layer_input(layer, r0); seg[1].lda = din;
-                seg[1].b = c->w[(size_t)3 * (layer - 1) + 1]; seg[1].ldb = dout; seg[1].k = din;
-            }
-            const int out_b16 = layer < c->L ? 1 : 0;      // logits stay fp32
-            char* out = c->act[(size_t)layer - 1] + r0 * (int64_t)dout * (out_b16 ? 2 : 4);
-            launch_gemm_bf16_nn(seg, sage ? 2 : 1, out, out_b16, dout, np, dout, ep, s);
-        }
-    }
-    c->fwd_done[(size_t)(layer - 1) * (size_t)M.k + (size_t)p] = 1;
+    const int64_t r0 = c->M.off[(size_t)p];
+    const int32_t dout = c->dims[(size_t)layer];
+    compute_fwd(c, layer, p, c->layer_input(layer, r0),
+                c->act[(size_t)layer - 1] + r0 * (int64_t)dout * c->act_es(layer), s);
+    c->fwd_done[(size_t)(layer - 1) * (size_t)c->M.k + (size_t)p] = 1;
     return check_launch(c, "gnn_layer_fwd");
 }
 
@@ -536,14 +545,15 @@ gnn_status gnn_loss(gnn_ctx* c, void* stream)
 {
     if (!c) return GNN_EINVAL;
     if (!c->bound) return c->fail(GNN_ESTATE, "buffers are not bound (call gnn_bind)");
+    if (c->streaming()) return c->fail(GNN_EUNSUPPORTED, "with a streaming budget only gnn_epoch drives the schedule");
     for (uint8_t f : c->fwd_done)
         if (!f) return c->fail(GNN_ESTATE, "gnn_loss before the forward pass has covered every (layer, partition)");
     hipStream_t s = (hipStream_t)stream;
     float* scal = (float*)(c->scratch + c->ws.scalars);
     {
         Timed t(c, s, GNN_K_LOSS);
-        launch_loss((const float*)c->act[(size_t)c->L - 1], c->labels, c->mask, c->gact[(size_t)c->L - 1], c->M.n,
-                    c->dims[(size_t)c->L], (unsigned long long*)(scal + 16),
+        launch_loss((const float*)c->act[(size_t)c->L - 1], c->labels, c->mask, c->gact[(size_t)c->L - 1],
+                    c->M.n, c->dims[(size_t)c->L], (unsigned long long*)(scal + 16),
                     (float*)(c->scratch + c->ws.losspart), scal, s);
     }
     c->loss_done = true;
@@ -575,96 +585,26 @@ gnn_status gnn_layer_bwd(gnn_ctx* c, int32_t layer, int32_t p, void* stream)
         return c->fail(GNN_ESTATE, "staging does not hold this (layer, partition); call gnn_gather_boundary first");
     hipStream_t s = (hipStream_t)stream;
     const HostMeta& M = c->M;
-    const int32_t L = c->L;
     const int64_t r0 = M.off[(size_t)p], np = M.off[(size_t)p + 1] - r0;
     const int64_t nb = M.boff[(size_t)p + 1] - M.boff[(size_t)p];
     const int32_t din = c->dims[(size_t)layer - 1], dout = c->dims[(size_t)layer];
-    const char* W = c->w[(size_t)3 * (layer - 1)];
-    const char* Ws = c->w[(size_t)3 * (layer - 1) + 1];
-    float* gW = c->gw[(size_t)3 * (layer - 1)];
-    float* gWs = c->gw[(size_t)3 * (layer - 1) + 1];
-    float* gb = c->has_bias ? c->gw[(size_t)3 * (layer - 1) + 2] : nullptr;
-    char* Z = c->scratch + c->ws.z;
-    char* dYbuf = c->scratch + c->ws.dy;
-    char* dZ = c->scratch + c->ws.dz;
-    float* dGA = (float*)(c->scratch + c->ws.dga);
-    float* partial = (float*)(c->scratch + c->ws.partial);
-    float* colpart = (float*)(c->scratch + c->ws.colpart);
-    const bool b16 = c->bf16();
-    const bool sage = c->model == GNN_SAGE_MEAN;
 
     // write-back buffer initialisation: first partition of this layer since gnn_loss
     if (layer >= 2 && c->bwd_done[(size_t)layer] == 0) {
         Timed t(c, s, GNN_K_OTHER);
         launch_fill_zero(c->gact[(size_t)layer - 2], M.n * (int64_t)din * 4, s);
     }
-    // activation backward: dY = grad A ⊙ [A > 0] on hidden layers, grad A itself on the last
-    const float* g = c->gact[(size_t)layer - 1] + r0 * dout;
-    const char* dY = (const char*)g;
-    {
-        Timed t(c, s, GNN_K_ACT_BWD);
-        if (b16) {
-            const char* a = layer < L ? c->act[(size_t)layer - 1] + r0 * (int64_t)dout * 2 : nullptr;
-            launch_act_bwd_bf16(g, a, dYbuf, np, dout, gb, colpart, s);
-            dY = dYbuf;
-        } else if (layer < L) {
-            launch_act_bwd(g, (const float*)c->act[(size_t)layer - 1] + r0 * dout, (float*)dYbuf, np,
-                           dout, gb, colpart, s);
-            dY = dYbuf;
-        } else {
-            launch_act_bwd(g, nullptr, nullptr, np, dout, gb, colpart, s);
-        }
-    }
-    // recompute the aggregate from the regathered rows
-    run_spmm_fwd(c, layer, p, s);
-    // weight gradients, summed over partitions
-    {
-        Timed t(c, s, GNN_K_GEMM_DW);
-        if (b16) {
-            launch_gemm_bf16_tn(Z, din, dY, dout, gW, dout, din, dout, np, partial, s);
-            if (sage)
-                launch_gemm_bf16_tn(c->layer_input(layer, r0), din, dY, dout, gWs, dout, din, dout, np,
-                                    partial, s);
-        } else {
-            launch_gemm_tn((const float*)Z, din, (const float*)dY, dout, gW, dout, din, dout, np, partial, s);
-            if (sage)
-                launch_gemm_tn((const float*)c->layer_input(layer, r0), din, (const float*)dY, dout, gWs,
-                               dout, din, dout, np, partial, s);
-        }
-    }
+    const char* act_own = c->act[(size_t)layer - 1] + r0 * (int64_t)dout * c->act_es(layer);
+    const char* dY = compute_bwd(c, layer, p, c->layer_input(layer, r0),
+                                 c->gact[(size_t)layer - 1] + r0 * dout, act_own, s);
     if (layer >= 2) {
         float* gprev = c->gact[(size_t)layer - 2];
         {
-            Timed t(c, s, GNN_K_GEMM_DZ);
-            GemmEpilogue ep;
-            if (b16) launch_gemm_bf16_nt(dY, dout, W, dout, dZ, 1, din, np, din, dout, ep, s);
-            else launch_gemm_nt((const float*)dY, dout, (const float*)W, dout, (float*)dZ, din, np, din, dout, ep, s);
-        }
-        {
-            const int64_t t0 = M.toff[(size_t)p];
-            const SpmmItems items = plan_items(M.plan_bwd, c->D.bwd, p);
-            float* segpart = (float*)(c->scratch + c->ws.segpart);
-            {
-                Timed t(c, s, GNN_K_SPMM_T);
-                launch_spmm(c->D.trp + t0, c->D.tcol, c->D.tw, nullptr, dZ, np, nullptr, dGA, np + nb,
-                            din, b16 ? 1 : 0, 0, items, segpart, s);
-            }
-            if (items.nlong > 0) {
-                Timed t(c, s, GNN_K_SPMM_REDUCE);
-                launch_spmm_reduce(nullptr, dGA, din, 0, items, segpart, s);
-            }
-        }
-        {
             Timed t(c, s, GNN_K_SCATTER);
-            launch_scatter_add(dGA, np + nb, np, r0, c->D.bnd + M.boff[(size_t)p], gprev, din, s);
+            launch_scatter_add((const float*)(c->scratch + c->ws.dga), np + nb, np, r0,
+                               c->D.bnd + M.boff[(size_t)p], gprev, din, s);
         }
-        if (sage) {
-            Timed t(c, s, GNN_K_GEMM_DZ);
-            GemmEpilogue ep;
-            ep.accumulate = 1;
-            if (b16) launch_gemm_bf16_nt(dY, dout, Ws, dout, gprev + r0 * din, 0, din, np, din, dout, ep, s);
-            else launch_gemm_nt((const float*)dY, dout, (const float*)Ws, dout, gprev + r0 * din, din, np, din, dout, ep, s);
-        }
+        compute_bwd_self(c, layer, p, dY, gprev + r0 * din, s);
     }
     c->bwd_done[(size_t)layer] += 1;
     return check_launch(c, "gnn_layer_bwd");
@@ -677,16 +617,13 @@ gnn_status gnn_epoch(gnn_ctx* c, void* stream, float* loss_out)
     hipStream_t s = (hipStream_t)stream;
     const int32_t L = c->L, k = c->M.k;
     c->events_used = 0;
-    gnn_status st;
-    {
-        Timed t(c, s, GNN_K_OTHER);
-        for (int32_t l = 0; l < L; ++l) {
-            const int64_t wsz = (int64_t)c->dims[(size_t)l] * c->dims[(size_t)l + 1] * 4;
-            launch_fill_zero(c->gw[(size_t)3 * l], wsz, s);
-            if (c->model == GNN_SAGE_MEAN) launch_fill_zero(c->gw[(size_t)3 * l + 1], wsz, s);
-            if (c->has_bias) launch_fill_zero(c->gw[(size_t)3 * l + 2], (int64_t)c->dims[(size_t)l + 1] * 4, s);
-        }
+    if (c->streaming()) {
+        gnn_status st = epoch_streaming(c, s, loss_out);
+        if (st == GNN_OK && c->prof) collect_profile(c);
+        return st;
     }
+    gnn_status st;
+    zero_weight_grads(c, s);
     for (int32_t l = 1; l <= L; ++l)
         for (int32_t p = 0; p < k; ++p) {
             if ((st = gnn_gather_boundary(c, l, p, stream)) != GNN_OK) return st;

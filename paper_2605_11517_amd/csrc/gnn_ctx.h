@@ -1,0 +1,160 @@
+// Context object behind the C ABI and the helpers shared by the resident and the streaming
+// schedule.
+#pragma once
+
+#include <memory>
+#include <string>
+#include <vector>
+
+#include "gnn_internal.h"
+
+namespace gnnmi {
+
+struct DevMeta {
+    int64_t* rp = nullptr;
+    int32_t* lcol = nullptr;
+    float* ew = nullptr;
+    float* rscale = nullptr;
+    int32_t* bnd = nullptr;
+    int32_t* bnd_local = nullptr;
+    int64_t* trp = nullptr;
+    int32_t* tcol = nullptr;
+    float* tw = nullptr;
+    int32_t* order = nullptr;
+    struct Plan {
+        int32_t* range_rows = nullptr;
+        int32_t* seg_row = nullptr;
+        int64_t* seg_begin = nullptr;
+        int32_t* seg_len = nullptr;
+        int32_t* long_row = nullptr;
+        int32_t* long_first = nullptr;
+        int32_t* long_nseg = nullptr;
+    } fwd, bwd;
+    bool ready = false;
+};
+
+struct Workspace {  // byte offsets into `scratch`
+    int64_t z = 0, dy = 0, dz = 0, dga = 0, partial = 0, colpart = 0, losspart = 0, scalars = 0,
+            segpart = 0;
+    int64_t staging_bytes = 0, scratch_bytes = 0;
+};
+
+struct StreamEngine;  // streaming.cpp
+
+}  // namespace gnnmi
+
+struct gnn_ctx {
+    int32_t model = 0, dtype = 0, L = 0, has_bias = 1;
+    int64_t hbm_budget = 0;              // 0: everything resident; else bytes of the block caches
+    std::vector<int32_t> dims;
+    mutable std::string err;
+    bool built = false, bound = false;
+    gnnmi::HostMeta M;
+    gnnmi::DevMeta D;
+    gnnmi::Workspace ws;
+    // bound buffers.  Resident mode: all device memory.  Streaming mode: feat / act / gact are
+    // pinned host memory, everything else device memory.
+    const char* feat = nullptr;          // dtype of the context
+    std::vector<char*> act;              // act[l-1]: dtype for l < L, fp32 for l = L
+    std::vector<float*> gact;
+    std::vector<const char*> w;          // W, W_s: dtype; b: fp32
+    std::vector<float*> gw;
+    const int32_t* labels = nullptr;
+    const uint8_t* mask = nullptr;
+    char* staging = nullptr;
+    char* scratch = nullptr;
+    // schedule state
+    int32_t staged_layer = -1, staged_p = -1;
+    std::vector<uint8_t> fwd_done;      // L * k
+    std::vector<int32_t> bwd_done;      // per layer: partitions finished since gnn_loss
+    bool loss_done = false;
+    gnnmi::StreamEngine* stream_engine = nullptr;
+    // profiling
+    bool prof = false;
+    std::vector<hipEvent_t> events;
+    std::vector<int> event_class;
+    size_t events_used = 0;
+    double prof_ms[GNN_K_COUNT] = {0};
+    int64_t prof_launches[GNN_K_COUNT] = {0};
+
+    gnn_status fail(gnn_status st, const std::string& msg) const
+    {
+        err = msg;
+        return st;
+    }
+    bool streaming() const { return hbm_budget != 0; }
+    bool bf16() const { return dtype == GNN_BF16; }
+    int64_t es() const { return dtype == GNN_BF16 ? 2 : 4; }   // bytes per stored activation/weight
+    // bytes per element of act[layer-1] (the logits are always fp32)
+    int64_t act_es(int32_t layer) const { return layer == L ? 4 : es(); }
+    // rows [r0, ...) of the input of `layer` (A^{layer-1}), width d_{layer-1}
+    const char* layer_input(int32_t layer, int64_t r0 = 0) const
+    {
+        const char* base = layer == 1 ? feat : act[(size_t)layer - 2];
+        return base + r0 * (int64_t)dims[(size_t)layer - 1] * es();
+    }
+};
+
+namespace gnnmi {
+
+// HIP-event bracket around one kernel class (only when profiling is on).
+struct Timed {
+    gnn_ctx* c;
+    hipStream_t s;
+    Timed(gnn_ctx* ctx, hipStream_t st, int cls) : c(ctx), s(st)
+    {
+        if (c->prof) mark(cls);
+    }
+    ~Timed()
+    {
+        if (c->prof) mark(-1);
+    }
+    void mark(int cls)
+    {
+        if (c->events_used == c->events.size()) {
+            hipEvent_t e;
+            if (hipEventCreate(&e) != hipSuccess) return;
+            c->events.push_back(e);
+            c->event_class.push_back(0);
+        }
+        c->event_class[c->events_used] = cls;
+        (void)hipEventRecord(c->events[c->events_used], s);
+        ++c->events_used;
+    }
+};
+
+inline gnn_status check_launch(gnn_ctx* c, const char* what)
+{
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return c->fail(GNN_EHIP, std::string(what) + ": " + hipGetErrorString(e));
+    return GNN_OK;
+}
+
+// The three compute steps of one (layer, partition) pair, on explicit row blocks.  The
+// resident schedule passes pointers into the caller's full arrays; the streaming schedule
+// passes cache slots and transfer buffers.
+
+// staging[run] = block[local rows] for the whole boundary list of p (resident: block = full A^{l-1})
+// is done by the schedules themselves.
+
+// A_p^l = act(Z_p W (+ X_p W_s) + b) with Z_p = S_p [in_own ; staging]; out_own has row stride d_l.
+void compute_fwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, char* out_own, hipStream_t s);
+
+// Activation backward, recompute of Z_p, weight/bias gradients (added into grad_w) and, for
+// layer >= 2, dZ_p and the gradient of the gathered rows (left in scratch, |R_p| x d_{l-1}
+// fp32).  Returns the dY_p block (dtype of the context; fp32 path: may alias g_own).
+const char* compute_bwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, const float* g_own,
+                        const char* act_own, hipStream_t s);
+// SAGE self term: gprev_own (n_p x d_{l-1} fp32) += dY_p W_s^T
+void compute_bwd_self(gnn_ctx* c, int32_t layer, int32_t p, const char* dY, float* gprev_own,
+                      hipStream_t s);
+
+void zero_weight_grads(gnn_ctx* c, hipStream_t s);
+void collect_profile(gnn_ctx* c);
+
+// streaming.cpp
+gnn_status stream_engine_create(gnn_ctx* c);
+void stream_engine_destroy(gnn_ctx* c);
+gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out);
+
+}  // namespace gnnmi

@@ -31,6 +31,9 @@ struct HostMeta {
     std::vector<int64_t> boff;      // k+1
     std::vector<int32_t> bnd;       // rows (library order), ascending inside a partition
     std::vector<int32_t> bnd_orig;  // same entries as original ids
+    // only when the streaming schedule is requested: B_p split by source partition
+    std::vector<int32_t> bnd_local; // row inside its source partition's block
+    std::vector<int64_t> brun;      // k * (k+1): brun[p*(k+1)+q] = first entry of B_p owned by q
     // transpose of S per partition: rows are the entries of R_p = [own_p ; B_p]
     std::vector<int64_t> toff;      // k+1, offset of partition p's rows in trp
     std::vector<int64_t> trp;       // sum |R_p| + 1, positions into tcol / tw
@@ -62,7 +65,7 @@ constexpr int32_t kSpmmRangeRows = 64;
 // Builds everything above.  Returns GNN_OK or an error with `err` set.
 gnn_status build_host_meta(int model, int64_t n, const int64_t* rowptr, const int32_t* colidx,
                            int32_t k, int32_t mode, uint64_t seed, const int32_t* user_part,
-                           HostMeta& out, std::string& err);
+                           bool want_runs, HostMeta& out, std::string& err);
 
 // ---- kernel launchers (all enqueue on `s`; sizes already validated by the caller) --------
 
@@ -168,7 +171,14 @@ int64_t act_bwd_partial_floats(int64_t rows, int32_t d);
 void launch_loss(const float* logits, const int32_t* labels, const uint8_t* mask, float* grad,
                  int64_t n, int32_t c, unsigned long long* count_dev, float* partial,
                  float* loss_dev, hipStream_t s);
-int64_t loss_partial_floats(int64_t n);
+int64_t loss_partial_floats(int64_t n, int32_t k);
+// the same in three steps, so that the rows can be processed block by block
+void launch_count_mask(const uint8_t* mask, int64_t n, unsigned long long* count_dev, hipStream_t s);
+int64_t launch_loss_rows(const float* logits, const int32_t* labels, const uint8_t* mask, float* grad,
+                         int64_t rows, int32_t c, const unsigned long long* count_dev, float* partial,
+                         hipStream_t s);   // returns the number of partial sums written
+void launch_loss_finish(const float* partial, int64_t nparts, const unsigned long long* count_dev,
+                        float* loss_dev, hipStream_t s);
 
 void launch_fill_zero(void* p, int64_t bytes, hipStream_t s);
 

@@ -255,22 +255,41 @@ __global__ __launch_bounds__(kBlock) void k_colsum_finish(const float* __restric
 
 }  // namespace
 
-int64_t loss_partial_floats(int64_t n) { return n / (kLossRowsPerWave * (kBlock / kWave)) + 2; }
+int64_t loss_partial_floats(int64_t n, int32_t k) { return n / (kLossRowsPerWave * (kBlock / kWave)) + k + 2; }
 
-void launch_loss(const float* logits, const int32_t* labels, const uint8_t* mask, float* grad,
-                 int64_t n, int32_t c, unsigned long long* count_dev, float* partial,
-                 float* loss_dev, hipStream_t s)
+void launch_count_mask(const uint8_t* mask, int64_t n, unsigned long long* count_dev, hipStream_t s)
 {
     launch_fill_zero(count_dev, sizeof(unsigned long long), s);
     int64_t cb = (n + kBlock * 64 - 1) / (kBlock * 64);
     hipLaunchKernelGGL(k_count_mask, dim3((unsigned)(cb < 1 ? 1 : cb)), dim3(kBlock), 0, s, mask, n,
                        count_dev);
+}
+
+int64_t launch_loss_rows(const float* logits, const int32_t* labels, const uint8_t* mask, float* grad,
+                         int64_t rows, int32_t c, const unsigned long long* count_dev, float* partial,
+                         hipStream_t s)
+{
+    if (rows <= 0) return 0;
     const int64_t rpb = kLossRowsPerWave * (kBlock / kWave);
-    const int64_t blocks = (n + rpb - 1) / rpb;
+    const int64_t blocks = (rows + rpb - 1) / rpb;
     hipLaunchKernelGGL(k_loss, dim3((unsigned)blocks), dim3(kBlock), 0, s, logits, labels, mask,
-                       grad, n, c, (const unsigned long long*)count_dev, partial);
-    hipLaunchKernelGGL(k_loss_finish, dim3(1), dim3(kBlock), 0, s, (const float*)partial, blocks,
-                       (const unsigned long long*)count_dev, loss_dev);
+                       grad, rows, c, count_dev, partial);
+    return blocks;
+}
+
+void launch_loss_finish(const float* partial, int64_t nparts, const unsigned long long* count_dev,
+                        float* loss_dev, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_loss_finish, dim3(1), dim3(kBlock), 0, s, partial, nparts, count_dev, loss_dev);
+}
+
+void launch_loss(const float* logits, const int32_t* labels, const uint8_t* mask, float* grad,
+                 int64_t n, int32_t c, unsigned long long* count_dev, float* partial,
+                 float* loss_dev, hipStream_t s)
+{
+    launch_count_mask(mask, n, count_dev, s);
+    const int64_t blocks = launch_loss_rows(logits, labels, mask, grad, n, c, count_dev, partial, s);
+    launch_loss_finish(partial, blocks, count_dev, loss_dev, s);
 }
 
 int64_t act_bwd_partial_floats(int64_t rows, int32_t d)

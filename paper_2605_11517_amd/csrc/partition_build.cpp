@@ -201,7 +201,7 @@ void append_plan(HostMeta::Plan& G, int32_t k, std::vector<PlanPart>& parts)
 
 gnn_status build_host_meta(int model, int64_t n, const int64_t* rowptr, const int32_t* colidx,
                            int32_t k, int32_t mode, uint64_t seed, const int32_t* user_part,
-                           HostMeta& M, std::string& err)
+                           bool want_runs, HostMeta& M, std::string& err)
 {
     if (!rowptr || n < 1) { err = "n must be >= 1 and rowptr non-null"; return GNN_EINVAL; }
     if (n > 0x7FFFFFF0ll) { err = "n exceeds the int32 vertex id range"; return GNN_EINVAL; }
@@ -364,6 +364,23 @@ gnn_status build_host_meta(int model, int64_t n, const int64_t* rowptr, const in
                 ++o;
             }
             std::vector<int32_t>().swap(bnd_p[(size_t)p]);
+        }
+
+        if (want_runs) {
+            // B_p is ascending in library row, i.e. grouped by source partition: record where
+            // each group starts and the row number inside the source partition's block
+            M.brun.assign((size_t)k * ((size_t)k + 1), 0);
+            M.bnd_local.resize(M.bnd.size());
+            parallel_for(k, 1, [&](int, int64_t p) {
+                const int32_t* b0 = M.bnd.data() + M.boff[(size_t)p];
+                const int32_t* b1 = M.bnd.data() + M.boff[(size_t)p + 1];
+                int64_t* run = M.brun.data() + (size_t)p * ((size_t)k + 1);
+                for (int32_t q = 0; q <= k; ++q)
+                    run[q] = std::lower_bound(b0, b1, (int32_t)M.off[(size_t)q]) - b0;
+                for (int32_t q = 0; q < k; ++q)
+                    for (int64_t i = run[q]; i < run[q + 1]; ++i)
+                        M.bnd_local[(size_t)(M.boff[(size_t)p] + i)] = b0[i] - (int32_t)M.off[(size_t)q];
+            });
         }
 
         // ---- phase C: transpose of every T_p ------------------------------------------------

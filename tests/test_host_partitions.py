@@ -130,7 +130,11 @@ def test_argument_errors_are_reported():
     assert e.value.status == 4
 
 
-def test_unsupported_requests_say_so():
+def test_streaming_budget_is_validated():
     with pytest.raises(GnnError) as e:
-        Context("gcn", (4, 3), hbm_budget_bytes=1 << 20)          # streaming schedule
-    assert e.value.status == 5
+        Context("gcn", (4, 3), hbm_budget_bytes=-1)
+    assert e.value.status == 1
+    rowptr, colidx = small_graph(30, 100, seed=1)
+    ctx = Context("gcn", (4, 3), hbm_budget_bytes=1 << 20)
+    ctx.build_partitions(rowptr, colidx, 3, "random")            # builds the per-source runs too
+    assert ctx.get_stats()["k"] == 3
