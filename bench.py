@@ -107,6 +107,9 @@ def main():
     ap.add_argument("--workload", default="mid")
     ap.add_argument("--cpu-sample-n", type=int, default=0, help="vertices of the oracle sample (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--hbm-budget-gb", type=float, default=0.0,
+                    help="> 0: run the streaming schedule (activations and gradients in pinned host "
+                         "memory) with this much HBM for the partition-block caches")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (a dispatch of known "
                          "size, used to scale hardware byte counters)")
@@ -134,7 +137,7 @@ def main():
     w = glorot_weights(dims, cfg["seed"], sage=(model == "sage"))
     t1 = time.perf_counter()
     s = Session(model, dims, rowptr, colidx, cfg["k"], cfg["part"], cfg["seed"], X, w, y, m,
-                dtype=cfg["dtype"])
+                dtype=cfg["dtype"], hbm_budget_bytes=int(args.hbm_budget_gb * 2 ** 30))
     es = 2 if cfg["dtype"] == "bf16" else 4
     mfma_peak = MFMA_BF16_PEAK_TFLOPS if cfg["dtype"] == "bf16" else MFMA_F32_PEAK_TFLOPS
     stats = s.ctx.get_stats()
@@ -179,7 +182,9 @@ def main():
         "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg["dtype"], "data": "synthetic",
-        "config": {"workload": args.workload, "n": n, "operator_entries": nnz, "model": model,
+        "config": {"workload": args.workload + ("" if not args.hbm_budget_gb else
+                                                 " (streaming, %.3g GiB block cache)" % args.hbm_budget_gb),
+                   "n": n, "operator_entries": nnz, "model": model,
                    "dims": list(dims), "k": stats["k"], "partitioner": cfg["part"],
                    "alpha": stats["sum_required"] / n, "sum_boundary": stats["sum_boundary"]},
         "loss": loss,
@@ -213,7 +218,7 @@ def main():
         from paper_2605_11517_amd.profiling import read_traffic
         table = read_traffic(os.path.join(ROOT, "profiles", "pmc_%s_epoch.md" % args.workload))
         if table:
-            rows = [v for k, v in table.items() if k.startswith("k_spmm_items")]
+            rows = [v for k, v in table.items() if k.startswith(("k_spmm_items", "k_spmm_slots"))]
             if rows:
                 tot_l = sum(r["launches"] for r in rows)
                 traffic = sum(r["bytes_per_launch"] * r["launches"] for r in rows) / tot_l
@@ -221,7 +226,8 @@ def main():
         upper = sum((2 if l == 0 else 3) * (stats["nnz"] * (4 + dims[l] * es) + n * dims[l] * es)
                     for l in range(L))
         out["roofline"] = {
-            "kernel": "k_spmm_items (aggregation over T_p and T_p^T: forward, recompute, transposed)",
+            "kernel": "k_spmm_slots / k_spmm_items (aggregation over T_p and T_p^T: forward, recompute, "
+                      "transposed; column-sliced variant where rows are whole 128-byte lines)",
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
             "bytes_per_launch": k_bytes / k_launches,

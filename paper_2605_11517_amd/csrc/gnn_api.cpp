@@ -41,6 +41,7 @@ void free_device(DevMeta& D)
         if (P->long_row) (void)hipFree(P->long_row);
         if (P->long_first) (void)hipFree(P->long_first);
         if (P->long_nseg) (void)hipFree(P->long_nseg);
+        if (P->rows_sorted) (void)hipFree(P->rows_sorted);
     }
     D = DevMeta{};
 }
@@ -82,6 +83,7 @@ gnn_status ensure_device(gnn_ctx* c)
         step(upload(P.long_row, H.long_row));
         step(upload(P.long_first, H.long_first));
         step(upload(P.long_nseg, H.long_nseg));
+        step(upload(P.rows_sorted, H.rows_sorted));
     }
     if (e != hipSuccess) {
         free_device(D);
@@ -150,6 +152,8 @@ SpmmItems plan_items(const HostMeta::Plan& H, const DevMeta::Plan& P, int32_t p)
     it.long_row = P.long_row ? P.long_row + l0 : nullptr;
     it.long_first = P.long_first ? P.long_first + l0 : nullptr;
     it.long_nseg = P.long_nseg ? P.long_nseg + l0 : nullptr;
+    it.nshort = H.rows_off[(size_t)p + 1] - H.rows_off[(size_t)p];
+    it.rows_sorted = P.rows_sorted ? P.rows_sorted + H.rows_off[(size_t)p] : nullptr;
     return it;
 }
 
@@ -167,7 +171,7 @@ void run_spmm_fwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, hipS
     {
         Timed t(c, s, GNN_K_SPMM);
         launch_spmm(c->D.rp + r0, c->D.lcol, c->D.ew, rscale, in_own, np, c->staging, Z, np, din, b16,
-                    b16, items, segpart, s);
+                    b16, items, segpart, 1, s);
     }
     if (items.nlong > 0) {
         Timed t(c, s, GNN_K_SPMM_REDUCE);
@@ -301,7 +305,7 @@ const char* compute_bwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own
         {
             Timed t(c, s, GNN_K_SPMM_T);
             launch_spmm(c->D.trp + t0, c->D.tcol, c->D.tw, nullptr, dZ, np, nullptr, dGA, np + nb, din,
-                        b16 ? 1 : 0, 0, items, segpart, s);
+                        b16 ? 1 : 0, 0, items, segpart, 0, s);
         }
         if (items.nlong > 0) {
             Timed t(c, s, GNN_K_SPMM_REDUCE);

@@ -29,6 +29,7 @@ struct DevMeta {
         int32_t* long_row = nullptr;
         int32_t* long_first = nullptr;
         int32_t* long_nseg = nullptr;
+        int32_t* rows_sorted = nullptr;
     } fwd, bwd;
     bool ready = false;
 };

@@ -54,6 +54,8 @@ struct HostMeta {
         std::vector<int32_t> long_first;  // its first segment (index local to the partition)
         std::vector<int32_t> long_nseg;   // its number of segments
         int64_t max_segs = 0;             // most segments in any partition
+        std::vector<int64_t> rows_off;    // k+1, offsets into rows_sorted
+        std::vector<int32_t> rows_sorted; // short rows (local ids) by entry count, longest first
     } plan_fwd, plan_bwd;
 };
 
@@ -93,13 +95,15 @@ struct SpmmItems {
     const int32_t* long_first = nullptr;
     const int32_t* long_nseg = nullptr;
     int64_t nlong = 0;
+    const int32_t* rows_sorted = nullptr;  // short rows, longest first (column-sliced kernel)
+    int64_t nshort = 0;
 };
 // a_rows / b_rows hold fp32 (in_bf16 = 0) or bfloat16 rows; out is fp32 or bfloat16; the sums
 // and `partial` are always fp32.
 void launch_spmm(const int64_t* rp, const int32_t* col, const float* w, const float* rowscale,
                  const void* a_rows, int64_t n_a, const void* b_rows, void* out, int64_t nrows,
                  int32_t d, int in_bf16, int out_bf16, const SpmmItems& items, float* partial,
-                 hipStream_t s);
+                 int column_slices /* allow the XCD column-sliced kernel */, hipStream_t s);
 // second step of the aggregation: combines the segment partial sums of the long rows
 void launch_spmm_reduce(const float* rowscale, void* out, int32_t d, int out_bf16,
                         const SpmmItems& items, float* partial, hipStream_t s);

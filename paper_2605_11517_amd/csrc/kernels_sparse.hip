@@ -4,6 +4,8 @@
 //   gather      staging[i,:] = A^{l-1}[B_p[i],:]                       (Gather / regather step)
 //   spmm        Z_p[v,:] = scale_v * sum_{e in row v} w_e * src(col_e)  (aggregation along T_p)
 //   scatter-add grad A^{l-1}[owner(i),:] += grad GA_p[i,:]              (scatter-accumulate step)
+#include <cstdlib>
+
 #include "gnn_internal.h"
 
 namespace gnnmi {
@@ -307,6 +309,116 @@ __global__ __launch_bounds__(kBlock) void k_spmm_items(const SpmmArgs g)
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Column-sliced variant for rows of at least two 128-byte lines.
+//
+// The row is cut into NS slices of G 16-byte vectors (a multiple of 128 bytes each) and
+// workgroup b handles slice b % NS.  Consecutive workgroups are dispatched to consecutive XCDs,
+// each with its own L2, so every XCD only ever sees one slice of every source row: the eight L2s
+// hold disjoint data instead of eight copies of the same hot rows, which multiplies the number
+// of source rows that stay cached by NS.
+//
+// To keep the per-row cost from growing by the same factor, a wavefront here works on 64 / G
+// items at once, one per slot of G lanes.  An item is a long-row segment or a whole short row;
+// the host lists the short rows longest first, so the slots of a wavefront run about the same
+// number of steps.  Each slot streams its own index/weight chunk (G entries) and walks it with
+// up to eight source-slice loads in flight.
+// ---------------------------------------------------------------------------------------------
+template <typename TIn, typename TOut, int G>
+__global__ __launch_bounds__(kBlock) void k_spmm_slots(const SpmmArgs g, int32_t nslices)
+{
+    constexpr int EPV = Elem<TIn>::EPV;
+    constexpr int S = kWave / G;
+    constexpr int UNROLL = G < 8 ? G : 8;
+    const int lane = threadIdx.x % kWave;
+    const int slot = lane / G, gl = lane % G;
+    unsigned blk = blockIdx.x;
+    const int coff = (int)(blk % (unsigned)nslices) * (G * EPV) + gl * EPV;   // this lane's columns
+    blk /= (unsigned)nslices;
+    const int64_t item = ((int64_t)blk * (kBlock / kWave) + threadIdx.x / kWave) * S + slot;
+
+    const TIn* a_rows = static_cast<const TIn*>(g.a_rows);
+    const TIn* b_rows = static_cast<const TIn*>(g.b_rows);
+    int64_t e_begin = 0;
+    int32_t len = 0;
+    int32_t row = -1;
+    if (item < g.it.nsegs) {
+        e_begin = g.it.seg_begin[item];
+        len = g.it.seg_len[item];
+    } else if (item < g.it.nsegs + g.it.nshort) {
+        row = g.it.rows_sorted[item - g.it.nsegs];
+        e_begin = g.rp[row];
+        len = (int32_t)(g.rp[row + 1] - e_begin);
+    }
+    // the longest slot of the wavefront sets the trip count and lends its entries to finished
+    // slots, so that every load below reads a real source row
+    int32_t maxlen = len;
+    int lead = slot;
+#pragma unroll
+    for (int m = G; m < kWave; m <<= 1) {
+        const int32_t ol = __shfl_xor(maxlen, m, kWave);
+        const int os = __shfl_xor(lead, m, kWave);
+        if (ol > maxlen || (ol == maxlen && os < lead)) { maxlen = ol; lead = os; }
+    }
+    float acc[EPV];
+#pragma unroll
+    for (int i = 0; i < EPV; ++i) acc[i] = 0.f;
+
+    for (int32_t e0 = 0; e0 < maxlen; e0 += G) {
+        int32_t my_c = 0;
+        float my_w = 0.f;
+        if (e0 + gl < len) {
+            my_c = g.col[e_begin + e0 + gl];
+            my_w = g.w ? g.w[e_begin + e0 + gl] : 1.f;
+        }
+        const int cnt = len - e0;                     // entries this slot still has (may be <= 0)
+        const int lead_cnt = maxlen - e0 < G ? maxlen - e0 : G;
+#pragma unroll
+        for (int j0 = 0; j0 < G; j0 += UNROLL) {
+            if (j0 >= lead_cnt) break;               // uniform across the wavefront
+            uint4 x[UNROLL];
+            float ww[UNROLL];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const int j = j0 + u;
+                const bool on = j < cnt;
+                const int src_lane = on ? slot * G + j : lead * G + (j < lead_cnt ? j : lead_cnt - 1);
+                const int32_t c = __shfl(my_c, src_lane, kWave);
+                const float wt = __shfl(my_w, src_lane, kWave);
+                ww[u] = on ? wt : 0.f;
+                const TIn* src = (c < g.n_a) ? a_rows + (int64_t)c * g.ld : b_rows + ((int64_t)c - g.n_a) * g.ld;
+                x[u] = *reinterpret_cast<const uint4*>(src + coff);
+            }
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                float f[EPV];
+                Elem<TIn>::unpack(x[u], f);
+                const bool on = (j0 + u) < cnt;
+#pragma unroll
+                for (int i = 0; i < EPV; ++i) acc[i] += on ? ww[u] * f[i] : 0.f;
+            }
+        }
+    }
+    if (item < g.it.nsegs) {
+        float* o = g.partial + item * (int64_t)g.ld + coff;
+#pragma unroll
+        for (int h = 0; h < EPV / 4; ++h)
+            *reinterpret_cast<float4*>(o + 4 * h) =
+                make_float4(acc[4 * h], acc[4 * h + 1], acc[4 * h + 2], acc[4 * h + 3]);
+    } else if (row >= 0) {
+        const float sc = g.rowscale ? g.rowscale[row] : 1.f;
+        TOut* o = static_cast<TOut*>(g.out) + row * (int64_t)g.ld + coff;
+        constexpr int OPV = Elem<TOut>::EPV;
+#pragma unroll
+        for (int h = 0; h < EPV / OPV; ++h) {
+            float f[OPV];
+#pragma unroll
+            for (int i = 0; i < OPV; ++i) f[i] = sc * acc[h * OPV + i];
+            *reinterpret_cast<uint4*>(o + h * OPV) = Elem<TOut>::pack(f);
+        }
+    }
+}
+
 // out[row,:] = rowscale[row] * (partial[first,:] + partial[first+1,:] + ...): one wavefront per
 // long row and 256-column block, segments added in ascending order (eight loads in flight per
 // lane).
@@ -404,11 +516,42 @@ namespace {
 template <typename TIn, typename TOut>
 void spmm_typed(const int64_t* rp, const int32_t* col, const float* w, const float* rowscale,
                 const void* a_rows, int64_t n_a, const void* b_rows, void* out, int32_t d,
-                const SpmmItems& items, float* partial, hipStream_t s)
+                const SpmmItems& items, float* partial, bool slices, hipStream_t s)
 {
     constexpr int EPV = Elem<TIn>::EPV;
-    const int64_t nitems = items.nsegs + items.nranges;
     const int wpb = kBlock / kWave;
+    // Column slices across XCDs.  Measured on the 2.4 M-vertex workload (1 KB rows): eight
+    // 128-byte slices raise the L2 hit rate from 33 % to 47 % but turn each row into eight
+    // separate DRAM accesses, and the fetch rate drops from 6.7 to 5.0 TB/s - no gain; slices of
+    // 256 bytes keep DRAM bursts long enough and make the forward aggregation 11 % faster.  The
+    // transposed operator consists mostly of rows with one or two entries, whose cost is per
+    // row and only grows with slicing (1.3x slower on 2 KB rows), so it is never sliced.
+    // So: forward only, slices of 256 to 512 bytes, at most eight.
+    static const bool use_slices = [] {
+        const char* e = std::getenv("GNNMI_SPMM_SLICES");
+        return !(e && e[0] == '0');
+    }();
+    const int64_t row_bytes = (int64_t)d * (int64_t)sizeof(TIn);
+    if (slices && use_slices && row_bytes % 512 == 0 && row_bytes <= 4096 && items.rows_sorted &&
+        d % Elem<TOut>::EPV == 0) {
+        int ns = 8;
+        while (ns > 1 && (row_bytes / ns < 256 || row_bytes % (ns * 256) != 0)) ns >>= 1;
+        const int G = (int)(row_bytes / ns / 16);   // 16-byte vectors per slice: 16 or 32
+        const int S = kWave / (G > 0 ? G : 1);
+        const int64_t n_items = items.nsegs + items.nshort;
+        const int64_t blocks = (n_items + (int64_t)wpb * S - 1) / ((int64_t)wpb * S);
+        if (ns > 1 && (G == 16 || G == 32) && blocks * ns < ((int64_t)1 << 31) && n_items > 0) {
+            SpmmArgs g;
+            g.rp = rp; g.col = col; g.w = w; g.rowscale = rowscale;
+            g.a_rows = a_rows; g.n_a = n_a; g.b_rows = b_rows; g.out = out; g.d = d; g.ld = d;
+            g.it = items; g.partial = partial;
+            const dim3 grid((unsigned)(blocks * ns));
+            if (G == 16) hipLaunchKernelGGL((k_spmm_slots<TIn, TOut, 16>), grid, dim3(kBlock), 0, s, g, ns);
+            else hipLaunchKernelGGL((k_spmm_slots<TIn, TOut, 32>), grid, dim3(kBlock), 0, s, g, ns);
+            return;
+        }
+    }
+    const int64_t nitems = items.nsegs + items.nranges;
     const dim3 grid((unsigned)((nitems + wpb - 1) / wpb));
     const dim3 block(kBlock);
     const bool vec = (d % EPV == 0) && (d % Elem<TOut>::EPV == 0);
@@ -461,15 +604,16 @@ void spmm_reduce_typed(const float* rowscale, void* out, int32_t d, const SpmmIt
 void launch_spmm(const int64_t* rp, const int32_t* col, const float* w, const float* rowscale,
                  const void* a_rows, int64_t n_a, const void* b_rows, void* out, int64_t nrows,
                  int32_t d, int in_bf16, int out_bf16, const SpmmItems& items, float* partial,
-                 hipStream_t s)
+                 int column_slices, hipStream_t s)
 {
     if (nrows <= 0 || d <= 0 || items.nsegs + items.nranges <= 0) return;
+    const bool sl = column_slices != 0;
     if (!in_bf16)
-        spmm_typed<float, float>(rp, col, w, rowscale, a_rows, n_a, b_rows, out, d, items, partial, s);
+        spmm_typed<float, float>(rp, col, w, rowscale, a_rows, n_a, b_rows, out, d, items, partial, sl, s);
     else if (out_bf16)
-        spmm_typed<uint16_t, uint16_t>(rp, col, w, rowscale, a_rows, n_a, b_rows, out, d, items, partial, s);
+        spmm_typed<uint16_t, uint16_t>(rp, col, w, rowscale, a_rows, n_a, b_rows, out, d, items, partial, sl, s);
     else
-        spmm_typed<uint16_t, float>(rp, col, w, rowscale, a_rows, n_a, b_rows, out, d, items, partial, s);
+        spmm_typed<uint16_t, float>(rp, col, w, rowscale, a_rows, n_a, b_rows, out, d, items, partial, sl, s);
 }
 
 void launch_spmm_reduce(const float* rowscale, void* out, int32_t d, int out_bf16,

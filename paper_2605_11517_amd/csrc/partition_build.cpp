@@ -142,7 +142,7 @@ void lp_round(int64_t n, const int64_t* rowptr, const int32_t* colidx, int32_t k
 // others are grouped into consecutive ranges holding at most kSpmmSegment entries and
 // kSpmmRangeRows rows (a long row closes the range before it and is skipped by range items).
 struct PlanPart {
-    std::vector<int32_t> range_rows, seg_row, seg_len, long_row, long_first, long_nseg;
+    std::vector<int32_t> range_rows, seg_row, seg_len, long_row, long_first, long_nseg, rows_sorted;
     std::vector<int64_t> seg_begin;
 };
 void plan_partition(const int64_t* rp, int64_t nrows, PlanPart& P)
@@ -173,6 +173,18 @@ void plan_partition(const int64_t* rp, int64_t nrows, PlanPart& P)
         acc += deg;
     }
     if (nrows > start) P.range_rows.push_back((int32_t)nrows);
+    // short rows by entry count, longest first, ascending row id among equals (counting sort)
+    std::vector<int64_t> bucket((size_t)kSpmmSegment + 2, 0);
+    for (int64_t r = 0; r < nrows; ++r) {
+        const int64_t deg = rp[r + 1] - rp[r];
+        if (deg <= kSpmmSegment) bucket[(size_t)(kSpmmSegment - deg) + 1]++;
+    }
+    for (size_t i = 1; i < bucket.size(); ++i) bucket[i] += bucket[i - 1];
+    P.rows_sorted.resize((size_t)bucket.back());
+    for (int64_t r = 0; r < nrows; ++r) {
+        const int64_t deg = rp[r + 1] - rp[r];
+        if (deg <= kSpmmSegment) P.rows_sorted[(size_t)bucket[(size_t)(kSpmmSegment - deg)]++] = (int32_t)r;
+    }
 }
 
 void append_plan(HostMeta::Plan& G, int32_t k, std::vector<PlanPart>& parts)
@@ -180,8 +192,11 @@ void append_plan(HostMeta::Plan& G, int32_t k, std::vector<PlanPart>& parts)
     G.range_off.assign((size_t)k + 1, 0);
     G.seg_off.assign((size_t)k + 1, 0);
     G.long_off.assign((size_t)k + 1, 0);
+    G.rows_off.assign((size_t)k + 1, 0);
     for (int32_t p = 0; p < k; ++p) {
         PlanPart& P = parts[(size_t)p];
+        G.rows_off[(size_t)p + 1] = G.rows_off[(size_t)p] + (int64_t)P.rows_sorted.size();
+        G.rows_sorted.insert(G.rows_sorted.end(), P.rows_sorted.begin(), P.rows_sorted.end());
         G.range_off[(size_t)p + 1] = G.range_off[(size_t)p] + (int64_t)P.range_rows.size();
         G.seg_off[(size_t)p + 1] = G.seg_off[(size_t)p] + (int64_t)P.seg_row.size();
         G.long_off[(size_t)p + 1] = G.long_off[(size_t)p] + (int64_t)P.long_row.size();
