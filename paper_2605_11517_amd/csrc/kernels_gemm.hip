@@ -18,6 +18,7 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int kThreads = 256;
 constexpr int BK = 16;
+constexpr int PF = 1;   // tiles of global loads in flight per thread
 constexpr int PAD = 4;
 
 struct Operand {         // a matrix operand restricted to one K segment
@@ -38,11 +39,15 @@ __device__ inline void load_kfast(const float* __restrict__ p, int64_t ld, int64
         const int64_t sidx = slow0 + (t >> 2) + 64 * i;
         const int32_t k = k0 + kq;
         float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (sidx < nslow) {
+        if (VEC) {
+            // unconditional load from a clamped (always valid) address, zeroed afterwards:
+            // without branches the compiler can keep several tiles of loads in flight
+            const float* q = p + (sidx < nslow ? sidx : nslow - 1) * ld + (k < kend ? k : k0);
+            const float4 x = *reinterpret_cast<const float4*>(q);
+            v = x;   // rows / k past the end are zeroed when the tile goes to LDS
+        } else if (sidx < nslow) {
             const float* q = p + sidx * ld + k;
-            if (VEC) {
-                if (k < kend) v = *reinterpret_cast<const float4*>(q);
-            } else {
+            {
                 if (k + 0 < kend) v.x = q[0];
                 if (k + 1 < kend) v.y = q[1];
                 if (k + 2 < kend) v.z = q[2];
@@ -83,11 +88,13 @@ __device__ inline void load_kslow(const float* __restrict__ p, int64_t ld, int64
         const int64_t k = k0 + t / TPR + KPP * i;
         const int64_t f = fast0 + fq;
         float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (k < kend) {
+        if (VEC) {
+            const float* q = p + (k < kend ? k : k0) * ld + (f < nfast ? f : fast0);
+            const float4 x = *reinterpret_cast<const float4*>(q);
+            v = x;   // rows / k past the end are zeroed when the tile goes to LDS
+        } else if (k < kend) {
             const float* q = p + k * ld + f;
-            if (VEC) {
-                if (f < nfast) v = *reinterpret_cast<const float4*>(q);
-            } else {
+            {
                 if (f + 0 < nfast) v.x = q[0];
                 if (f + 1 < nfast) v.y = q[1];
                 if (f + 2 < nfast) v.z = q[2];
@@ -125,6 +132,30 @@ __device__ inline void load_fragment(const float* S, int x, int half, float (&f)
 #pragma unroll
         for (int j = 0; j < 8; ++j) f[j] = S[(8 * half + j) * (BT + PAD) + x];
     }
+}
+
+// Zero the vectors of a tile that lie past the end of the matrix (their loads were clamped to
+// valid addresses).  Done when the registers are written to LDS, not at load time, so that the
+// loads of several tiles stay in flight.
+template <int BT>
+__device__ inline void mask_kfast(int64_t slow0, int64_t nslow, int64_t k0, int64_t kend, float4 (&r)[BT / 64])
+{
+    const int t = threadIdx.x;
+    const int64_t k = k0 + (t & 3) * 4;
+#pragma unroll
+    for (int i = 0; i < BT / 64; ++i)
+        if (!(slow0 + (t >> 2) + 64 * i < nslow && k < kend)) r[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+}
+template <int BT>
+__device__ inline void mask_kslow(int64_t k0, int64_t kend, int64_t fast0, int64_t nfast, float4 (&r)[BT / 64])
+{
+    constexpr int TPR = BT / 4;
+    constexpr int KPP = kThreads / TPR;
+    const int t = threadIdx.x;
+    const int64_t f = fast0 + (t % TPR) * 4;
+#pragma unroll
+    for (int i = 0; i < BT / 64; ++i)
+        if (!(k0 + t / TPR + KPP * i < kend && f < nfast)) r[i] = make_float4(0.f, 0.f, 0.f, 0.f);
 }
 
 struct GemmArgs {
@@ -179,8 +210,11 @@ __global__ __launch_bounds__(kThreads) void k_gemm(const GemmArgs g)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    float4 ra[BM / 64], rb[BN / 64];
-    auto load_tile = [&](int64_t t) {
+    // Register ring of PF tiles: the global loads of tile t + PF are issued while tile t is
+    // multiplied, so that a load has PF tile-times to arrive (one tile-time is far shorter than
+    // the memory latency, above all with the fast bf16 MFMA).
+    float4 ra[PF][BM / 64], rb[PF][BN / 64];
+    auto load_tile = [&](int64_t t, float4 (&ra)[BM / 64], float4 (&rb)[BN / 64]) {
         const int seg = t < tiles0 ? 0 : 1;
         const int64_t k0 = seg == 0 ? kbeg + t * BK : (t - tiles0) * BK;
         const int64_t kend = seg == 0 ? kend0 : (int64_t)g.kseg[1];
@@ -189,19 +223,35 @@ __global__ __launch_bounds__(kThreads) void k_gemm(const GemmArgs g)
         if (B_KFAST) load_kfast<BN, VEC_B>(g.b[seg].p, g.b[seg].ld, n0, g.n, (int32_t)k0, (int32_t)kend, rb);
         else load_kslow<BN, VEC_B>(g.b[seg].p, g.b[seg].ld, k0, kend, n0, g.n, rb);
     };
-    auto store_tile = [&](int buf) {
-        if (A_KFAST) store_kfast<BM>(As[buf], ra); else store_kslow<BM>(As[buf], ra);
-        if (B_KFAST) store_kfast<BN>(Bs[buf], rb); else store_kslow<BN>(Bs[buf], rb);
+    auto store_tile = [&](int buf, int64_t t, const float4 (&ra_in)[BM / 64], const float4 (&rb_in)[BN / 64]) {
+        const int seg = t < tiles0 ? 0 : 1;
+        const int64_t k0 = seg == 0 ? kbeg + t * BK : (t - tiles0) * BK;
+        const int64_t kend = seg == 0 ? kend0 : (int64_t)g.kseg[1];
+        float4 ra[BM / 64], rb[BN / 64];
+#pragma unroll
+        for (int i = 0; i < BM / 64; ++i) ra[i] = ra_in[i];
+#pragma unroll
+        for (int i = 0; i < BN / 64; ++i) rb[i] = rb_in[i];
+        if (A_KFAST) { mask_kfast<BM>(m0, g.m, k0, kend, ra); store_kfast<BM>(As[buf], ra); }
+        else { mask_kslow<BM>(k0, kend, m0, g.m, ra); store_kslow<BM>(As[buf], ra); }
+        if (B_KFAST) { mask_kfast<BN>(n0, g.n, k0, kend, rb); store_kfast<BN>(Bs[buf], rb); }
+        else { mask_kslow<BN>(k0, kend, n0, g.n, rb); store_kslow<BN>(Bs[buf], rb); }
     };
 
-    if (ntiles > 0) {
-        load_tile(0);
-        store_tile(0);
-    }
+#pragma unroll
+    for (int d = 0; d < PF; ++d)
+        if (ntiles > 0) load_tile(d < ntiles ? d : ntiles - 1, ra[d], rb[d]);
+    if (ntiles > 0) store_tile(0, 0, ra[0], rb[0]);
     __syncthreads();
-    for (int64_t t = 0; t < ntiles; ++t) {
-        const int buf = (int)(t & 1);
-        if (t + 1 < ntiles) load_tile(t + 1);
+    for (int64_t t0 = 0; t0 < ntiles; t0 += PF) {
+#pragma unroll
+        for (int dd = 0; dd < PF; ++dd) {
+            const int64_t t = t0 + dd;
+            if (t >= ntiles) break;
+            const int buf = (int)(t & 1);
+            // slot dd held tile t, already in LDS; past the end the last tile is fetched again
+            // (never used) so that the load stream has no branches
+            load_tile(t + PF < ntiles ? t + PF : ntiles - 1, ra[dd], rb[dd]);
         const int half = lane >> 5, xl = lane & 31;
         float af[TM][8], bf[TN][8];
 #pragma unroll
@@ -215,8 +265,9 @@ __global__ __launch_bounds__(kThreads) void k_gemm(const GemmArgs g)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i][st], bf[j][st], acc[i][j], 0, 0, 0);
-        if (t + 1 < ntiles) store_tile(buf ^ 1);
-        __syncthreads();
+            if (t + 1 < ntiles) store_tile(buf ^ 1, t + 1, ra[(dd + 1) % PF], rb[(dd + 1) % PF]);
+            __syncthreads();
+        }
     }
 
     // epilogue: lane holds C[8 (r/4) + 4 (lane/32) + r%4][lane%32] of each 32x32 tile

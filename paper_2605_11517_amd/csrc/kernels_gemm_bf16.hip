@@ -6,10 +6,13 @@
 //             grad W^l += Z_p^T dY_p                          bf16 x bf16 -> fp32, split-K
 //
 // A workgroup of 4 wavefronts (2 x 2) owns a BM x BN tile of C and walks K in steps of 32.
-// Both operands sit in LDS as [row][k] with k contiguous, because an MFMA lane consumes eight
-// consecutive k of its row as one 16-byte register group.  Operands that are k-contiguous in
-// memory are copied with 16-byte loads and stores; operands that are row-contiguous in memory
-// (W in the forward product, both operands of Z^T dY) are transposed on the way into LDS.
+// An MFMA lane consumes eight consecutive k of its row as one 16-byte register group.
+// Operands that are k-contiguous in memory are kept [row][k] in LDS and fetched with one
+// 16-byte read per fragment.  Operands that are row-contiguous in memory (W in the forward
+// product, both operands of Z^T dY) are kept as they come, [k][row], and a fragment is
+// gathered with eight 2-byte reads down a column; consecutive lanes then read consecutive
+// rows, which is conflict-free, whereas transposing on the way into LDS would put the sixteen
+// lanes of a k-row on one bank.
 #include "gnn_internal.h"
 
 namespace gnnmi {
@@ -21,7 +24,9 @@ typedef uint16_t bf16_t;
 
 constexpr int kThreads = 256;
 constexpr int BK = 32;
-constexpr int LDK = BK + 8;   // LDS row stride in elements (80 bytes: conflict-free 16-byte reads)
+constexpr int PF = 1;         // tiles of global loads in flight per thread
+constexpr int LDK = BK + 8;   // k-fast tiles: [row][k], row stride 80 bytes (conflict-free 16-byte reads)
+constexpr int XPAD = 4;       // k-slow tiles: [k][row], row stride BT + 4 elements
 
 __device__ inline float bf16_to_float(uint32_t h) { return __uint_as_float(h << 16); }
 __device__ inline uint32_t float_to_bf16(float f)
@@ -42,11 +47,15 @@ __device__ inline void load_kfast(const bf16_t* __restrict__ p, int64_t ld, int6
         const int64_t sidx = slow0 + (t >> 2) + 64 * i;
         const int64_t k = k0 + kq;
         uint4 v = make_uint4(0, 0, 0, 0);
-        if (sidx < nslow) {
+        if (VEC) {
+            // unconditional load from a clamped (always valid) address, zeroed afterwards:
+            // without branches the compiler can keep several tiles of loads in flight
+            const bf16_t* q = p + (sidx < nslow ? sidx : nslow - 1) * ld + (k < kend ? k : k0);
+            const uint4 x = *reinterpret_cast<const uint4*>(q);
+            v = x;   // rows / k past the end are zeroed when the tile goes to LDS
+        } else if (sidx < nslow) {
             const bf16_t* q = p + sidx * ld + k;
-            if (VEC) {
-                if (k < kend) v = *reinterpret_cast<const uint4*>(q);
-            } else {
+            {
                 uint32_t e[8];
 #pragma unroll
                 for (int j = 0; j < 8; ++j) e[j] = (k + j < kend) ? q[j] : 0u;
@@ -81,11 +90,13 @@ __device__ inline void load_kslow(const bf16_t* __restrict__ p, int64_t ld, int6
         const int64_t k = k0 + t / TPR + KPP * i;
         const int64_t f = fast0 + fq;
         uint4 v = make_uint4(0, 0, 0, 0);
-        if (k < kend) {
+        if (VEC) {
+            const bf16_t* q = p + (k < kend ? k : k0) * ld + (f < nfast ? f : fast0);
+            const uint4 x = *reinterpret_cast<const uint4*>(q);
+            v = x;   // rows / k past the end are zeroed when the tile goes to LDS
+        } else if (k < kend) {
             const bf16_t* q = p + k * ld + f;
-            if (VEC) {
-                if (f < nfast) v = *reinterpret_cast<const uint4*>(q);
-            } else {
+            {
                 uint32_t e[8];
 #pragma unroll
                 for (int j = 0; j < 8; ++j) e[j] = (f + j < nfast) ? q[j] : 0u;
@@ -96,7 +107,7 @@ __device__ inline void load_kslow(const bf16_t* __restrict__ p, int64_t ld, int6
         r[i] = v;
     }
 }
-// transposing store: element j of the vector belongs to LDS row fq + j, column k
+// k-slow tiles stay [k][x] in LDS: two 8-byte stores per vector (rows are 8-byte aligned)
 template <int BT>
 __device__ inline void store_kslow(bf16_t* S, const uint4 (&r)[BT / 64])
 {
@@ -106,14 +117,48 @@ __device__ inline void store_kslow(bf16_t* S, const uint4 (&r)[BT / 64])
     const int fq = (t % TPR) * 8;
 #pragma unroll
     for (int i = 0; i < BT / 64; ++i) {
-        const int k = t / TPR + KPP * i;
-        const uint32_t w[4] = {r[i].x, r[i].y, r[i].z, r[i].w};
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            S[(fq + 2 * j) * LDK + k] = (bf16_t)(w[j] & 0xFFFFu);
-            S[(fq + 2 * j + 1) * LDK + k] = (bf16_t)(w[j] >> 16);
-        }
+        bf16_t* dst = S + (t / TPR + KPP * i) * (BT + XPAD) + fq;
+        *reinterpret_cast<uint2*>(dst) = make_uint2(r[i].x, r[i].y);
+        *reinterpret_cast<uint2*>(dst + 4) = make_uint2(r[i].z, r[i].w);
     }
+}
+
+// The eight consecutive k (k8 .. k8 + 7) of row x as one MFMA operand register group.
+template <int BT, bool KFAST>
+__device__ inline bf16x8 load_fragment(const bf16_t* S, int x, int k8)
+{
+    if (KFAST) {
+        return *reinterpret_cast<const bf16x8*>(S + x * LDK + k8);
+    } else {
+        union { bf16_t h[8]; bf16x8 v; } u;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) u.h[j] = S[(k8 + j) * (BT + XPAD) + x];
+        return u.v;
+    }
+}
+
+// Zero the vectors of a tile that lie past the end of the matrix (their loads were clamped to
+// valid addresses).  Done when the registers are written to LDS, not at load time, so that the
+// loads of several tiles stay in flight.
+template <int BT>
+__device__ inline void mask_kfast(int64_t slow0, int64_t nslow, int64_t k0, int64_t kend, uint4 (&r)[BT / 64])
+{
+    const int t = threadIdx.x;
+    const int64_t k = k0 + (t & 3) * 8;
+#pragma unroll
+    for (int i = 0; i < BT / 64; ++i)
+        if (!(slow0 + (t >> 2) + 64 * i < nslow && k < kend)) r[i] = make_uint4(0, 0, 0, 0);
+}
+template <int BT>
+__device__ inline void mask_kslow(int64_t k0, int64_t kend, int64_t fast0, int64_t nfast, uint4 (&r)[BT / 64])
+{
+    constexpr int TPR = BT / 8;
+    constexpr int KPP = kThreads / TPR;
+    const int t = threadIdx.x;
+    const int64_t f = fast0 + (t % TPR) * 8;
+#pragma unroll
+    for (int i = 0; i < BT / 64; ++i)
+        if (!(k0 + t / TPR + KPP * i < kend && f < nfast)) r[i] = make_uint4(0, 0, 0, 0);
 }
 
 struct Args {
@@ -135,8 +180,10 @@ __global__ __launch_bounds__(kThreads) void k_gemm_bf16(const Args g)
 {
     constexpr int WM = BM / 2, WN = BN / 2;
     constexpr int TM = WM / 32, TN = WN / 32;
-    __shared__ __attribute__((aligned(16))) bf16_t As[2][BM * LDK];
-    __shared__ __attribute__((aligned(16))) bf16_t Bs[2][BN * LDK];
+    constexpr int A_TILE = A_KFAST ? BM * LDK : BK * (BM + XPAD);
+    constexpr int B_TILE = B_KFAST ? BN * LDK : BK * (BN + XPAD);
+    __shared__ __attribute__((aligned(16))) bf16_t As[2][A_TILE];
+    __shared__ __attribute__((aligned(16))) bf16_t Bs[2][B_TILE];
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -163,8 +210,11 @@ __global__ __launch_bounds__(kThreads) void k_gemm_bf16(const Args g)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    uint4 ra[BM / 64], rb[BN / 64];
-    auto load_tile = [&](int64_t t) {
+    // Register ring of PF tiles: the global loads of tile t + PF are issued while tile t is
+    // multiplied, so that a load has PF tile-times to arrive (one tile-time is far shorter than
+    // the memory latency, above all with the fast bf16 MFMA).
+    uint4 ra[PF][BM / 64], rb[PF][BN / 64];
+    auto load_tile = [&](int64_t t, uint4 (&ra)[BM / 64], uint4 (&rb)[BN / 64]) {
         const int seg = t < tiles0 ? 0 : 1;
         const int64_t k0 = seg == 0 ? kbeg + t * BK : (t - tiles0) * BK;
         const int64_t kend = seg == 0 ? kend0 : (int64_t)g.kseg[1];
@@ -173,37 +223,54 @@ __global__ __launch_bounds__(kThreads) void k_gemm_bf16(const Args g)
         if (B_KFAST) load_kfast<BN, VEC_B>(g.b[seg], g.ldb[seg], n0, g.n, k0, kend, rb);
         else load_kslow<BN, VEC_B>(g.b[seg], g.ldb[seg], k0, kend, n0, g.n, rb);
     };
-    auto store_tile = [&](int buf) {
-        if (A_KFAST) store_kfast<BM>(As[buf], ra); else store_kslow<BM>(As[buf], ra);
-        if (B_KFAST) store_kfast<BN>(Bs[buf], rb); else store_kslow<BN>(Bs[buf], rb);
+    auto store_tile = [&](int buf, int64_t t, const uint4 (&ra_in)[BM / 64], const uint4 (&rb_in)[BN / 64]) {
+        const int seg = t < tiles0 ? 0 : 1;
+        const int64_t k0 = seg == 0 ? kbeg + t * BK : (t - tiles0) * BK;
+        const int64_t kend = seg == 0 ? kend0 : (int64_t)g.kseg[1];
+        uint4 ra[BM / 64], rb[BN / 64];
+#pragma unroll
+        for (int i = 0; i < BM / 64; ++i) ra[i] = ra_in[i];
+#pragma unroll
+        for (int i = 0; i < BN / 64; ++i) rb[i] = rb_in[i];
+        if (A_KFAST) { mask_kfast<BM>(m0, g.m, k0, kend, ra); store_kfast<BM>(As[buf], ra); }
+        else { mask_kslow<BM>(k0, kend, m0, g.m, ra); store_kslow<BM>(As[buf], ra); }
+        if (B_KFAST) { mask_kfast<BN>(n0, g.n, k0, kend, rb); store_kfast<BN>(Bs[buf], rb); }
+        else { mask_kslow<BN>(k0, kend, n0, g.n, rb); store_kslow<BN>(Bs[buf], rb); }
     };
 
-    if (ntiles > 0) {
-        load_tile(0);
-        store_tile(0);
-    }
+#pragma unroll
+    for (int d = 0; d < PF; ++d)
+        if (ntiles > 0) load_tile(d < ntiles ? d : ntiles - 1, ra[d], rb[d]);
+    if (ntiles > 0) store_tile(0, 0, ra[0], rb[0]);
     __syncthreads();
-    for (int64_t t = 0; t < ntiles; ++t) {
-        const int buf = (int)(t & 1);
-        if (t + 1 < ntiles) load_tile(t + 1);
+    for (int64_t t0 = 0; t0 < ntiles; t0 += PF) {
+#pragma unroll
+        for (int dd = 0; dd < PF; ++dd) {
+            const int64_t t = t0 + dd;
+            if (t >= ntiles) break;
+            const int buf = (int)(t & 1);
+            // slot dd held tile t, already in LDS; past the end the last tile is fetched again
+            // (never used) so that the load stream has no branches
+            load_tile(t + PF < ntiles ? t + PF : ntiles - 1, ra[dd], rb[dd]);
         const int half = lane >> 5, xl = lane & 31;
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
             bf16x8 av[TM], bv[TN];
 #pragma unroll
             for (int i = 0; i < TM; ++i)
-                av[i] = *reinterpret_cast<const bf16x8*>(&As[buf][(wm0 + 32 * i + xl) * LDK + 16 * ks + 8 * half]);
+                av[i] = load_fragment<BM, A_KFAST>(As[buf], wm0 + 32 * i + xl, 16 * ks + 8 * half);
 #pragma unroll
             for (int j = 0; j < TN; ++j)
-                bv[j] = *reinterpret_cast<const bf16x8*>(&Bs[buf][(wn0 + 32 * j + xl) * LDK + 16 * ks + 8 * half]);
+                bv[j] = load_fragment<BN, B_KFAST>(Bs[buf], wn0 + 32 * j + xl, 16 * ks + 8 * half);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bv[j], acc[i][j], 0, 0, 0);
         }
-        if (t + 1 < ntiles) store_tile(buf ^ 1);
-        __syncthreads();
+            if (t + 1 < ntiles) store_tile(buf ^ 1, t + 1, ra[(dd + 1) % PF], rb[(dd + 1) % PF]);
+            __syncthreads();
+        }
     }
 
     // lane holds C[8 (r/4) + 4 (lane/32) + r%4][lane%32] of each 32x32 tile
