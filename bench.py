@@ -29,7 +29,7 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def algorithmic_bytes(stats, dims, model, n_parts, es=4):
+def algorithmic_bytes(stats, dims, model, n_parts, es=4, fused_scatter=False):
     """HBM bytes the method has to move per epoch, by kernel class (lower bound: every needed
     source row is read once per partition).  es = bytes per stored activation (4 fp32, 2 bf16);
     gradients of activations are always fp32."""
@@ -49,8 +49,13 @@ def algorithmic_bytes(stats, dims, model, n_parts, es=4):
         spmm = per_entry * nnz + 8 * (n + k) + sum_r * row + n * row + (4 * n if model == "sage" else 0)
         out["spmm"] += 2 * spmm
         if l >= 2:
-            out["spmm_t"] += 8 * nnz + 8 * (sum_r + k) + n * row + sum_r * grow
-            out["scatter"] += 3 * sum_r * grow + 4 * sum_b
+            if fused_scatter:
+                # transposed aggregation adds its rows straight onto their owners: read dZ once,
+                # read-modify-write every required row of grad A^{l-1}
+                out["spmm_t"] += 8 * nnz + 8 * (sum_r + k) + n * row + 2 * sum_r * grow + 4 * sum_b
+            else:
+                out["spmm_t"] += 8 * nnz + 8 * (sum_r + k) + n * row + sum_r * grow
+                out["scatter"] += 3 * sum_r * grow + 4 * sum_b
     return out
 
 
@@ -190,7 +195,8 @@ def main():
         "loss": loss,
     }
     if prof:
-        ab = algorithmic_bytes(stats, dims, model, stats["k"], es)
+        ab = algorithmic_bytes(stats, dims, model, stats["k"], es,
+                               fused_scatter=prof.get("scatter", (0, 0))[1] == 0)
         fl = gemm_flops(stats, dims, model)
         classes = {}
         for name, (ms, launches) in prof.items():

@@ -3,6 +3,7 @@
 // backward: regather, BW, scatter-accumulate).
 #include <algorithm>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 
@@ -171,11 +172,11 @@ void run_spmm_fwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, hipS
     {
         Timed t(c, s, GNN_K_SPMM);
         launch_spmm(c->D.rp + r0, c->D.lcol, c->D.ew, rscale, in_own, np, c->staging, Z, np, din, b16,
-                    b16, items, segpart, 1, s);
+                    b16, items, segpart, 1, SpmmScatter{}, s);
     }
     if (items.nlong > 0) {
         Timed t(c, s, GNN_K_SPMM_REDUCE);
-        launch_spmm_reduce(rscale, Z, din, b16, items, segpart, s);
+        launch_spmm_reduce(rscale, Z, din, b16, items, segpart, SpmmScatter{}, s);
     }
 }
 
@@ -243,7 +244,7 @@ void compute_fwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, char*
 }
 
 const char* compute_bwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, const float* g_own,
-                        const char* act_own, hipStream_t s)
+                        const char* act_own, float* fused_gprev, hipStream_t s)
 {
     const HostMeta& M = c->M;
     const int32_t L = c->L;
@@ -302,14 +303,25 @@ const char* compute_bwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own
         const int64_t t0 = M.toff[(size_t)p];
         const SpmmItems items = plan_items(M.plan_bwd, c->D.bwd, p);
         float* segpart = (float*)(c->scratch + c->ws.segpart);
+        // With fused_gprev the transposed aggregation adds each row of the gathered-row gradient
+        // straight onto its owner row of grad A^{l-1} (own rows in place, boundary rows through
+        // B_p) instead of writing it to scratch for a separate scatter-add pass.
+        SpmmScatter sc;
+        float* out = dGA;
+        if (fused_gprev) {
+            sc.n_own = np;
+            sc.base_row = M.off[(size_t)p];
+            sc.idx = c->D.bnd + M.boff[(size_t)p];
+            out = fused_gprev;
+        }
         {
             Timed t(c, s, GNN_K_SPMM_T);
-            launch_spmm(c->D.trp + t0, c->D.tcol, c->D.tw, nullptr, dZ, np, nullptr, dGA, np + nb, din,
-                        b16 ? 1 : 0, 0, items, segpart, 0, s);
+            launch_spmm(c->D.trp + t0, c->D.tcol, c->D.tw, nullptr, dZ, np, nullptr, out, np + nb, din,
+                        b16 ? 1 : 0, 0, items, segpart, 0, sc, s);
         }
         if (items.nlong > 0) {
             Timed t(c, s, GNN_K_SPMM_REDUCE);
-            launch_spmm_reduce(nullptr, dGA, din, 0, items, segpart, s);
+            launch_spmm_reduce(nullptr, out, din, 0, items, segpart, sc, s);
         }
     }
     return dY;
@@ -599,11 +611,17 @@ gnn_status gnn_layer_bwd(gnn_ctx* c, int32_t layer, int32_t p, void* stream)
         launch_fill_zero(c->gact[(size_t)layer - 2], M.n * (int64_t)din * 4, s);
     }
     const char* act_own = c->act[(size_t)layer - 1] + r0 * (int64_t)dout * c->act_es(layer);
+    // scatter-accumulate of the gathered-row gradient: fused into the transposed aggregation
+    // (GNNMI_FUSE_SCATTER=0 keeps it a separate pass over a scratch copy)
+    static const bool fuse = [] {
+        const char* e = std::getenv("GNNMI_FUSE_SCATTER");
+        return !(e && e[0] == '0');
+    }();
+    float* gprev = layer >= 2 ? c->gact[(size_t)layer - 2] : nullptr;
     const char* dY = compute_bwd(c, layer, p, c->layer_input(layer, r0),
-                                 c->gact[(size_t)layer - 1] + r0 * dout, act_own, s);
+                                 c->gact[(size_t)layer - 1] + r0 * dout, act_own, fuse ? gprev : nullptr, s);
     if (layer >= 2) {
-        float* gprev = c->gact[(size_t)layer - 2];
-        {
+        if (!fuse) {
             Timed t(c, s, GNN_K_SCATTER);
             launch_scatter_add((const float*)(c->scratch + c->ws.dga), np + nb, np, r0,
                                c->D.bnd + M.boff[(size_t)p], gprev, din, s);

@@ -98,15 +98,24 @@ struct SpmmItems {
     const int32_t* rows_sorted = nullptr;  // short rows, longest first (column-sliced kernel)
     int64_t nshort = 0;
 };
+// Optional fused scatter-accumulate for fp32 outputs: instead of out[r,:] = value, the kernel
+// does out[map(r),:] += value with map(r) = base_row + r for r < n_own and idx[r - n_own]
+// otherwise.  n_own < 0 switches it off.
+struct SpmmScatter {
+    int64_t n_own = -1;
+    int64_t base_row = 0;
+    const int32_t* idx = nullptr;
+};
 // a_rows / b_rows hold fp32 (in_bf16 = 0) or bfloat16 rows; out is fp32 or bfloat16; the sums
 // and `partial` are always fp32.
 void launch_spmm(const int64_t* rp, const int32_t* col, const float* w, const float* rowscale,
                  const void* a_rows, int64_t n_a, const void* b_rows, void* out, int64_t nrows,
                  int32_t d, int in_bf16, int out_bf16, const SpmmItems& items, float* partial,
-                 int column_slices /* allow the XCD column-sliced kernel */, hipStream_t s);
+                 int column_slices /* allow the XCD column-sliced kernel */, const SpmmScatter& sc,
+                 hipStream_t s);
 // second step of the aggregation: combines the segment partial sums of the long rows
 void launch_spmm_reduce(const float* rowscale, void* out, int32_t d, int out_bf16,
-                        const SpmmItems& items, float* partial, hipStream_t s);
+                        const SpmmItems& items, float* partial, const SpmmScatter& sc, hipStream_t s);
 
 // dst[map(i),:] += src[i,:] with map(i) = base_row + i for i < n_own, idx[i - n_own] otherwise.
 void launch_scatter_add(const float* src, int64_t nrows, int64_t n_own, int64_t base_row,

@@ -109,6 +109,15 @@ struct SpmmArgs {
     int32_t d, ld;          // d: columns handled by this launch; ld: row stride (elements)
     SpmmItems it;
     float* partial;         // always fp32
+    // optional fused scatter-accumulate (fp32 output only): row r is ADDED to output row
+    // map_base + r when r < map_n_own, else to row map_idx[r - map_n_own]; map_n_own < 0 = off
+    int64_t map_n_own, map_base;
+    const int32_t* map_idx;
+    __device__ int64_t out_row(int32_t r) const
+    {
+        if (map_n_own < 0) return r;
+        return r < map_n_own ? map_base + r : (int64_t)map_idx[r - map_n_own];
+    }
 };
 
 // 16-byte vectors of the storage types: 4 floats or 8 bfloat16 (kept as raw uint16_t).
@@ -248,7 +257,8 @@ __device__ inline void spmm_accumulate(const SpmmArgs& g, int64_t e_begin, int64
 // columns per vector, which is a whole 16-byte store for TOut = TIn and two for fp32 output of
 // a bf16 input.
 template <typename TOut, int EPV, int G, int NV, bool VEC>
-__device__ inline void spmm_store(TOut* o, int32_t d, int lane, float sc, const float (&acc)[NV][EPV])
+__device__ inline void spmm_store(TOut* o, int32_t d, int lane, float sc, const float (&acc)[NV][EPV],
+                                  bool add = false)
 {
     if (lane >= G) return;
 #pragma unroll
@@ -262,12 +272,23 @@ __device__ inline void spmm_store(TOut* o, int32_t d, int lane, float sc, const 
                 float f[OPV];
 #pragma unroll
                 for (int i = 0; i < OPV; ++i) f[i] = sc * acc[v][h * OPV + i];
-                *reinterpret_cast<uint4*>(o + c0 + h * OPV) = Elem<TOut>::pack(f);
+                uint4* dst = reinterpret_cast<uint4*>(o + c0 + h * OPV);
+                if (add) {
+                    float old[OPV];
+                    Elem<TOut>::unpack(*dst, old);
+#pragma unroll
+                    for (int i = 0; i < OPV; ++i) f[i] += old[i];
+                }
+                *dst = Elem<TOut>::pack(f);
             }
         } else {
 #pragma unroll
             for (int i = 0; i < EPV; ++i)
-                if (c0 + i < d) Elem<TOut>::store(o + c0 + i, sc * acc[v][i]);
+                if (c0 + i < d) {
+                    float v2 = sc * acc[v][i];
+                    if (add) v2 += Elem<TOut>::load(o + c0 + i);
+                    Elem<TOut>::store(o + c0 + i, v2);
+                }
         }
     }
 }
@@ -304,8 +325,8 @@ __global__ __launch_bounds__(kBlock) void k_spmm_items(const SpmmArgs g)
 #pragma unroll
             for (int i = 0; i < EPV; ++i) acc[v][i] = 0.f;
         spmm_accumulate<TIn, G, NV, VEC>(g, e_begin, e_end, lane, acc);
-        spmm_store<TOut, EPV, G, NV, VEC>(static_cast<TOut*>(g.out) + row * (int64_t)g.ld, g.d, lane,
-                                          g.rowscale ? g.rowscale[row] : 1.f, acc);
+        spmm_store<TOut, EPV, G, NV, VEC>(static_cast<TOut*>(g.out) + g.out_row(row) * (int64_t)g.ld, g.d,
+                                          lane, g.rowscale ? g.rowscale[row] : 1.f, acc, g.map_n_own >= 0);
     }
 }
 
@@ -434,7 +455,8 @@ __global__ __launch_bounds__(kBlock) void k_spmm_long_reduce(const SpmmArgs g)
     const int32_t ns = g.it.long_nseg[i];
     const float sc = g.rowscale ? g.rowscale[row] : 1.f;
     const int32_t cb = blockIdx.y * 256;          // first column of this block
-    TOut* out = static_cast<TOut*>(g.out) + row * (int64_t)g.ld;
+    TOut* out = static_cast<TOut*>(g.out) + g.out_row(row) * (int64_t)g.ld;
+    const bool add = g.map_n_own >= 0;
     if (VEC) {
         const int32_t c = cb + lane * 4;
         if (c >= g.d) return;
@@ -449,15 +471,19 @@ __global__ __launch_bounds__(kBlock) void k_spmm_long_reduce(const SpmmArgs g)
 #pragma unroll
             for (int u = 0; u < U; ++u) { s.x += x[u].x; s.y += x[u].y; s.z += x[u].z; s.w += x[u].w; }
         }
-        Elem<TOut>::store(out + c + 0, sc * s.x);
-        Elem<TOut>::store(out + c + 1, sc * s.y);
-        Elem<TOut>::store(out + c + 2, sc * s.z);
-        Elem<TOut>::store(out + c + 3, sc * s.w);
+        float o4[4] = {sc * s.x, sc * s.y, sc * s.z, sc * s.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (add) o4[e] += Elem<TOut>::load(out + c + e);
+            Elem<TOut>::store(out + c + e, o4[e]);
+        }
     } else {
         for (int32_t c = cb + lane; c < g.d && c < cb + 256; c += kWave) {
             float s = 0.f;
             for (int32_t t = 0; t < ns; ++t) s += g.partial[(first + t) * (int64_t)g.ld + c];
-            Elem<TOut>::store(out + c, sc * s);
+            s *= sc;
+            if (add) s += Elem<TOut>::load(out + c);
+            Elem<TOut>::store(out + c, s);
         }
     }
 }
@@ -516,7 +542,8 @@ namespace {
 template <typename TIn, typename TOut>
 void spmm_typed(const int64_t* rp, const int32_t* col, const float* w, const float* rowscale,
                 const void* a_rows, int64_t n_a, const void* b_rows, void* out, int32_t d,
-                const SpmmItems& items, float* partial, bool slices, hipStream_t s)
+                const SpmmItems& items, float* partial, bool slices, const SpmmScatter& sc,
+                hipStream_t s)
 {
     constexpr int EPV = Elem<TIn>::EPV;
     const int wpb = kBlock / kWave;
@@ -532,7 +559,7 @@ void spmm_typed(const int64_t* rp, const int32_t* col, const float* w, const flo
         return !(e && e[0] == '0');
     }();
     const int64_t row_bytes = (int64_t)d * (int64_t)sizeof(TIn);
-    if (slices && use_slices && row_bytes % 512 == 0 && row_bytes <= 4096 && items.rows_sorted &&
+    if (slices && sc.n_own < 0 && use_slices && row_bytes % 512 == 0 && row_bytes <= 4096 && items.rows_sorted &&
         d % Elem<TOut>::EPV == 0) {
         int ns = 8;
         while (ns > 1 && (row_bytes / ns < 256 || row_bytes % (ns * 256) != 0)) ns >>= 1;
@@ -545,6 +572,7 @@ void spmm_typed(const int64_t* rp, const int32_t* col, const float* w, const flo
             g.rp = rp; g.col = col; g.w = w; g.rowscale = rowscale;
             g.a_rows = a_rows; g.n_a = n_a; g.b_rows = b_rows; g.out = out; g.d = d; g.ld = d;
             g.it = items; g.partial = partial;
+            g.map_n_own = -1; g.map_base = 0; g.map_idx = nullptr;
             const dim3 grid((unsigned)(blocks * ns));
             if (G == 16) hipLaunchKernelGGL((k_spmm_slots<TIn, TOut, 16>), grid, dim3(kBlock), 0, s, g, ns);
             else hipLaunchKernelGGL((k_spmm_slots<TIn, TOut, 32>), grid, dim3(kBlock), 0, s, g, ns);
@@ -565,6 +593,7 @@ void spmm_typed(const int64_t* rp, const int32_t* col, const float* w, const flo
         g.b_rows = b_rows ? static_cast<const TIn*>(b_rows) + c0 : nullptr;
         g.out = static_cast<TOut*>(out) + c0; g.d = dc; g.ld = d; g.it = items;
         g.partial = partial + c0;
+        g.map_n_own = sc.n_own; g.map_base = sc.base_row; g.map_idx = sc.idx;
         const int nv = (dc + EPV - 1) / EPV;  // 16-byte vectors per row in this block
 #define GNN_SPMM(G, NV, VEC) \
     hipLaunchKernelGGL((k_spmm_items<TIn, TOut, G, NV, VEC>), grid, block, 0, s, g)
@@ -589,11 +618,12 @@ void spmm_typed(const int64_t* rp, const int32_t* col, const float* w, const flo
 
 template <typename TOut>
 void spmm_reduce_typed(const float* rowscale, void* out, int32_t d, const SpmmItems& items,
-                       float* partial, hipStream_t s)
+                       float* partial, const SpmmScatter& sc, hipStream_t s)
 {
     const int wpb = kBlock / kWave;
     SpmmArgs g{};
     g.rowscale = rowscale; g.out = out; g.d = d; g.ld = d; g.it = items; g.partial = partial;
+    g.map_n_own = sc.n_own; g.map_base = sc.base_row; g.map_idx = sc.idx;
     const dim3 rgrid((unsigned)((items.nlong + wpb - 1) / wpb), (unsigned)((d + 255) / 256));
     if (d % 4 == 0) hipLaunchKernelGGL((k_spmm_long_reduce<TOut, true>), rgrid, dim3(kBlock), 0, s, g);
     else hipLaunchKernelGGL((k_spmm_long_reduce<TOut, false>), rgrid, dim3(kBlock), 0, s, g);
@@ -604,24 +634,24 @@ void spmm_reduce_typed(const float* rowscale, void* out, int32_t d, const SpmmIt
 void launch_spmm(const int64_t* rp, const int32_t* col, const float* w, const float* rowscale,
                  const void* a_rows, int64_t n_a, const void* b_rows, void* out, int64_t nrows,
                  int32_t d, int in_bf16, int out_bf16, const SpmmItems& items, float* partial,
-                 int column_slices, hipStream_t s)
+                 int column_slices, const SpmmScatter& sc, hipStream_t s)
 {
     if (nrows <= 0 || d <= 0 || items.nsegs + items.nranges <= 0) return;
     const bool sl = column_slices != 0;
     if (!in_bf16)
-        spmm_typed<float, float>(rp, col, w, rowscale, a_rows, n_a, b_rows, out, d, items, partial, sl, s);
+        spmm_typed<float, float>(rp, col, w, rowscale, a_rows, n_a, b_rows, out, d, items, partial, sl, sc, s);
     else if (out_bf16)
-        spmm_typed<uint16_t, uint16_t>(rp, col, w, rowscale, a_rows, n_a, b_rows, out, d, items, partial, sl, s);
+        spmm_typed<uint16_t, uint16_t>(rp, col, w, rowscale, a_rows, n_a, b_rows, out, d, items, partial, sl, sc, s);
     else
-        spmm_typed<uint16_t, float>(rp, col, w, rowscale, a_rows, n_a, b_rows, out, d, items, partial, sl, s);
+        spmm_typed<uint16_t, float>(rp, col, w, rowscale, a_rows, n_a, b_rows, out, d, items, partial, sl, sc, s);
 }
 
 void launch_spmm_reduce(const float* rowscale, void* out, int32_t d, int out_bf16,
-                        const SpmmItems& items, float* partial, hipStream_t s)
+                        const SpmmItems& items, float* partial, const SpmmScatter& sc, hipStream_t s)
 {
     if (items.nlong <= 0 || d <= 0) return;
-    if (out_bf16) spmm_reduce_typed<uint16_t>(rowscale, out, d, items, partial, s);
-    else spmm_reduce_typed<float>(rowscale, out, d, items, partial, s);
+    if (out_bf16) spmm_reduce_typed<uint16_t>(rowscale, out, d, items, partial, sc, s);
+    else spmm_reduce_typed<float>(rowscale, out, d, items, partial, sc, s);
 }
 
 void launch_scatter_add(const float* src, int64_t nrows, int64_t n_own, int64_t base_row,

@@ -468,7 +468,7 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
             if (p + 1 < k && (st = load_io(p + 1)) != GNN_OK) return st;
             GNN_HIP(hipStreamWaitEvent(s, E.in_ready[ib], 0));
             const char* dY = compute_bwd(c, l, p, E.actc.ptr(own), (const float*)E.ginbuf(ib),
-                                         l < L ? E.ainbuf(ib) : nullptr, s);
+                                         l < L ? E.ainbuf(ib) : nullptr, nullptr, s);
             if ((st = mark_used(c, E.actc, own, s, false)) != GNN_OK) return st;
             E.actc.slots[(size_t)own].pinned = false;
             if (need_prev) {
