@@ -239,12 +239,17 @@ def main():
             "bytes_per_launch": k_bytes / k_launches,
             "avg_launch_ms": k_ms / k_launches, "launches_per_epoch": k_launches / args.steps,
             "no_reuse_bytes_per_launch": upper * args.steps / k_launches,
+            "traffic_GBps": None if traffic is None else traffic / (k_ms / k_launches * 1e-3) / 1e9,
             "note": "achieved = bytes the method must move if every needed source row is read "
                     "once per partition, over the HIP-event time of the kernel; traffic = measured "
                     "fetch+write bytes per launch (rocprofv3 counters); no_reuse = one source row "
                     "read per operator entry",
         }
         out["profiled_ms_per_step"] = sum(v[0] for v in prof.values()) / args.steps
+    if args.hbm_budget_gb:
+        st = s.ctx.get_stream_stats()              # of the last epoch
+        st["pcie_GBps"] = (st["h2d_bytes"] + st["d2h_bytes"]) / (ms_per_step * 1e-3) / 1e9
+        out["streaming"] = st
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_sample_n, log)
     out["paper_context"] = ("paper reports whole-system epochs only (SSD+PCIe bound): 7.2 s for a "

@@ -222,6 +222,18 @@ gnn_status gnn_set_profiling(gnn_ctx *ctx, int32_t enabled);
 gnn_status gnn_get_profile(const gnn_ctx *ctx, double *ms /* GNN_K_COUNT */,
                            int64_t *launches /* GNN_K_COUNT */);
 
+/* Traffic of the last streaming-schedule epoch (partition-wise cache; appendix on I/O
+ * optimisations): block loads host -> HBM and cache hits of the activation cache and of the
+ * gradient write-back cache, gradient blocks written back, and the bytes both directions
+ * moved in total (cache traffic plus the per-partition transfer buffers).  All zero after a
+ * resident epoch.  GNN_EINVAL on null arguments. */
+typedef struct {
+    int64_t act_loads, act_hits;
+    int64_t grad_loads, grad_hits, grad_writebacks;
+    int64_t h2d_bytes, d2h_bytes;
+} gnn_stream_stats;
+gnn_status gnn_get_stream_stats(const gnn_ctx *ctx, gnn_stream_stats *out);
+
 #ifdef __cplusplus
 }
 #endif

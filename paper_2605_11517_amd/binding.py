@@ -43,6 +43,11 @@ class _Stats(C.Structure):
                 ("max_own", C.c_int64), ("max_boundary", C.c_int64), ("max_nnz", C.c_int64)]
 
 
+class StreamStats(C.Structure):
+    _fields_ = [(f, C.c_int64) for f in ("act_loads", "act_hits", "grad_loads", "grad_hits",
+                                         "grad_writebacks", "h2d_bytes", "d2h_bytes")]
+
+
 def load_library():
     """Loads ``libgnnmi.so`` from the package directory (build it with
     ``python -m paper_2605_11517_amd.build``).  Raises if it is missing."""
@@ -74,6 +79,7 @@ def load_library():
         "gnn_epoch": [vp, vp, P(C.c_float)],
         "gnn_set_profiling": [vp, i32],
         "gnn_get_profile": [vp, P(C.c_double), P(i64)],
+        "gnn_get_stream_stats": [vp, P(StreamStats)],
     }
     for name, args in sig.items():
         fn = getattr(lib, name)
@@ -207,6 +213,11 @@ class Context:
 
     def set_profiling(self, enabled):
         self._check(self.lib.gnn_set_profiling(self.h, 1 if enabled else 0))
+
+    def get_stream_stats(self):
+        st = StreamStats()
+        self._check(self.lib.gnn_get_stream_stats(self.h, C.byref(st)))
+        return {name: int(getattr(st, name)) for name, _ in StreamStats._fields_}
 
     def get_profile(self):
         ms = (C.c_double * len(KERNEL_CLASSES))()

@@ -680,4 +680,11 @@ gnn_status gnn_get_profile(const gnn_ctx* c, double* ms, int64_t* launches)
     return GNN_OK;
 }
 
+gnn_status gnn_get_stream_stats(const gnn_ctx* c, gnn_stream_stats* out)
+{
+    if (!c || !out) return GNN_EINVAL;
+    *out = c->stream_stats;
+    return GNN_OK;
+}
+
 }  // extern "C"

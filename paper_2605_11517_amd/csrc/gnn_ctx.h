@@ -77,6 +77,7 @@ struct gnn_ctx {
     size_t events_used = 0;
     double prof_ms[GNN_K_COUNT] = {0};
     int64_t prof_launches[GNN_K_COUNT] = {0};
+    gnn_stream_stats stream_stats{};
 
     gnn_status fail(gnn_status st, const std::string& msg) const
     {

@@ -5,7 +5,11 @@
 // caching; overlap design in the appendix on I/O optimisations), with HBM in the role of the
 // host cache and pinned host memory in the role of storage:
 //   - for layer l only blocks of layer l-1 are cached, loaded when a partition depends on them
-//     and evicted least-recently-used, whole blocks at a time;
+//     and evicted whole blocks at a time.  The order in which blocks are needed is fixed by
+//     the partition dependencies (partition p touches its own block, then the owners of its
+//     boundary rows in ascending order), so the victim is the block whose next use lies
+//     furthest ahead; least-recently-used would evict exactly the block needed next whenever
+//     the partitions depend on more blocks than the cache holds;
 //   - the boundary list of a partition is ordered by source partition, so the gather walks it
 //     one cached block at a time ("a single lookup per partition");
 //   - outputs A_p^l bypass the cache: they go from a transfer buffer straight to their host
@@ -17,6 +21,8 @@
 // The arithmetic per partition is the resident schedule's, kernel for kernel, so results are
 // bit-identical to it.
 #include <algorithm>
+#include <climits>
+#include <cstdint>
 #include <cstring>
 
 #include "gnn_ctx.h"
@@ -45,6 +51,7 @@ struct BlockCache {
     std::vector<uint8_t> touched;   // write-back cache: block exists (on host or in a slot)
     char* host = nullptr;           // backing array of the current layer
     bool writeback = false;
+    int32_t cur_p = 0;              // partition whose accesses are being issued
     int64_t tick = 0;
     int64_t loads = 0, hits = 0, writebacks = 0;
     char* ptr(int32_t s) const { return pool + (int64_t)s * slot_bytes; }
@@ -57,6 +64,10 @@ struct StreamEngine {
     char* pool = nullptr;           // hbm_budget bytes, carved into the two caches per layer
     int64_t pool_bytes = 0;
     BlockCache actc, gradc;
+    // next_dep[p * k + b] = first partition p' >= p that touches block b (k if none); row k is all k
+    std::vector<int32_t> next_dep;
+    int32_t k = 0;
+    int64_t h2d_bytes = 0, d2h_bytes = 0;   // of the running epoch
     char* io = nullptr;             // 6 transfer buffers
     int64_t io_bytes = 0;           // bytes of one buffer
     hipEvent_t out_ready[2]{}, out_done[2]{}, in_ready[2]{}, in_released[2]{};
@@ -117,18 +128,46 @@ gnn_status write_back(gnn_ctx* c, StreamEngine& E, BlockCache& bc, int32_t s)
     sl.has_flushed = true;
     sl.dirty = false;
     ++bc.writebacks;
+    E.d2h_bytes += np * bc.row_bytes;
     return GNN_OK;
 }
 
-// Chooses a slot for a new block: a free one, else the least recently used unpinned one.
-int32_t pick_victim(const BlockCache& bc)
+// Position of "partition p touches block b" in the access order of a layer: partition by
+// partition, the own block first, then the other blocks in ascending order.
+inline int64_t access_pos(int32_t k, int32_t p, int32_t b)
 {
+    return (int64_t)p * (k + 1) + (b == p ? 0 : (int64_t)b + 1);
+}
+
+// Position of the first access to block b after position `now` of partition cur_p.
+int64_t next_use(const StreamEngine& E, int32_t cur_p, int64_t now, int32_t b)
+{
+    const int32_t k = E.k;
+    if (E.next_dep[(size_t)cur_p * k + b] == cur_p) {
+        const int64_t here = access_pos(k, cur_p, b);
+        if (here > now) return here;
+    }
+    const int32_t p2 = E.next_dep[(size_t)(cur_p + 1) * k + b];
+    return p2 >= k ? INT64_MAX : access_pos(k, p2, b);
+}
+
+// Chooses a slot for block `part`: a free one, else the unpinned one whose block is needed
+// again last (ties: the least recently used).
+int32_t pick_victim(const StreamEngine& E, const BlockCache& bc, int32_t part)
+{
+    const int64_t now = access_pos(E.k, bc.cur_p, part);
     int32_t best = -1;
+    int64_t best_next = -1;
     for (int32_t s = 0; s < bc.nslots; ++s) {
         const Slot& sl = bc.slots[(size_t)s];
         if (sl.part < 0) return s;
         if (sl.pinned) continue;
-        if (best < 0 || sl.last_use < bc.slots[(size_t)best].last_use) best = s;
+        const int64_t nu = next_use(E, bc.cur_p, now, sl.part);
+        if (best < 0 || nu > best_next ||
+            (nu == best_next && sl.last_use < bc.slots[(size_t)best].last_use)) {
+            best = s;
+            best_next = nu;
+        }
     }
     return best;
 }
@@ -144,7 +183,7 @@ gnn_status acquire(gnn_ctx* c, StreamEngine& E, BlockCache& bc, int32_t part, hi
     if (s >= 0) {
         ++bc.hits;
     } else {
-        s = pick_victim(bc);
+        s = pick_victim(E, bc, part);
         if (s < 0) {
             if (!wait) { *slot_out = -1; return GNN_OK; }
             return c->fail(GNN_ENOMEM, "streaming cache: every slot is pinned");
@@ -173,6 +212,7 @@ gnn_status acquire(gnn_ctx* c, StreamEngine& E, BlockCache& bc, int32_t part, hi
             GNN_HIP(hipEventRecord(sl.ready, E.h2d));
             sl.has_ready = true;
             ++bc.loads;
+            E.h2d_bytes += np * bc.row_bytes;
         }
         sl.part = part;
         sl.dirty = false;
@@ -203,6 +243,7 @@ gnn_status gather_from_cache(gnn_ctx* c, StreamEngine& E, int32_t layer, int32_t
     const HostMeta& M = c->M;
     const int32_t k = M.k;
     const int64_t row_bytes = (int64_t)c->dims[(size_t)layer - 1] * c->es();
+    E.actc.cur_p = p;
     gnn_status st = acquire(c, E, E.actc, p, s, true, own_slot);
     if (st != GNN_OK) return st;
     E.actc.slots[(size_t)*own_slot].pinned = true;
@@ -231,6 +272,7 @@ gnn_status prefetch_for(gnn_ctx* c, StreamEngine& E, int32_t p, hipStream_t s)
     const int64_t* run = M.brun.data() + (size_t)p * ((size_t)k + 1);
     int32_t budget = E.actc.nslots - 1;      // never cycle the whole cache for a prefetch
     int32_t slot;
+    E.actc.cur_p = p;
     gnn_status st = acquire(c, E, E.actc, p, s, false, &slot);
     if (st != GNN_OK) return st;
     --budget;
@@ -254,6 +296,18 @@ gnn_status stream_engine_create(gnn_ctx* c)
     StreamEngine* E = new (std::nothrow) StreamEngine();
     if (!E) return c->fail(GNN_ENOMEM, "out of host memory");
     c->stream_engine = E;
+    {
+        const int32_t k = M.k;
+        E->k = k;
+        E->next_dep.assign(((size_t)k + 1) * (size_t)k, k);
+        for (int32_t p = k - 1; p >= 0; --p) {
+            const int64_t* run = M.brun.data() + (size_t)p * ((size_t)k + 1);
+            for (int32_t b = 0; b < k; ++b) {
+                const bool dep = b == p || run[b + 1] > run[b];
+                E->next_dep[(size_t)p * k + b] = dep ? p : E->next_dep[(size_t)(p + 1) * k + b];
+            }
+        }
+    }
     int64_t dmax = 0;
     for (int32_t d : c->dims) dmax = std::max<int64_t>(dmax, d);
     E->io_bytes = (std::max<int64_t>(1, M.stats.max_own * dmax * 4) + 255) / 256 * 256;
@@ -345,6 +399,8 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
         for (Slot& sl : bc->slots) sl.has_ready = sl.has_released = sl.has_flushed = false;
     E.has_out_done[0] = E.has_out_done[1] = false;
     E.has_in_released[0] = E.has_in_released[1] = false;
+    E.h2d_bytes = E.d2h_bytes = 0;
+    for (BlockCache* bc : {&E.actc, &E.gradc}) bc->loads = bc->hits = bc->writebacks = 0;
 
     zero_weight_grads(c, s);
 
@@ -365,6 +421,7 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
         GNN_HIP(hipEventRecord(E.out_ready[ob], s));
         GNN_HIP(hipStreamWaitEvent(E.d2h, E.out_ready[ob], 0));
         if (bytes > 0) GNN_HIP(hipMemcpyAsync(dst, E.outbuf(ob), (size_t)bytes, hipMemcpyDeviceToHost, E.d2h));
+        E.d2h_bytes += bytes;
         GNN_HIP(hipEventRecord(E.out_done[ob], E.d2h));
         E.has_out_done[ob] = true;
         return GNN_OK;
@@ -404,6 +461,7 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
     auto load_in = [&](char* dst, const char* src, int64_t bytes, int ib, bool first) -> gnn_status {
         if (first && E.has_in_released[ib]) GNN_HIP(hipStreamWaitEvent(E.h2d, E.in_released[ib], 0));
         if (bytes > 0) GNN_HIP(hipMemcpyAsync(dst, src, (size_t)bytes, hipMemcpyHostToDevice, E.h2d));
+        E.h2d_bytes += bytes;
         return GNN_OK;
     };
     {
@@ -435,7 +493,22 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
         const int32_t din = c->dims[(size_t)l - 1], dout = c->dims[(size_t)l];
         const int64_t act_row = (int64_t)dout * c->act_es(l);
         const bool need_prev = l >= 2;
-        const int64_t act_pool = need_prev ? E.pool_bytes / 2 / 256 * 256 : E.pool_bytes;
+        // Split of the pool between the two caches.  A gradient block that is evicted costs a
+        // write-back and a reload, an activation block only a reload: when every gradient
+        // block of the layer fits beside two activation blocks the gradient cache gets them
+        // all, otherwise two thirds of the pool.
+        int64_t act_pool = E.pool_bytes;
+        if (need_prev) {
+            const int64_t a_slot = (max_np * din * c->es() + 255) / 256 * 256;
+            const int64_t g_slot = (max_np * din * 4 + 255) / 256 * 256;
+            int64_t grad_pool = (int64_t)k * g_slot;
+            if (E.pool_bytes - grad_pool < 2 * a_slot) {
+                grad_pool = E.pool_bytes / 3 * 2 / 256 * 256;
+                grad_pool = std::min(grad_pool, E.pool_bytes - 2 * a_slot);
+                grad_pool = std::max(grad_pool, 2 * g_slot);
+            }
+            act_pool = (E.pool_bytes - grad_pool) / 256 * 256;
+        }
         st = configure(c, E.actc, E.pool, act_pool, max_np * din * c->es(), (int64_t)din * c->es(),
                        const_cast<char*>(c->layer_input(l)), false);
         if (st != GNN_OK) return st;
@@ -477,6 +550,7 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
                 const int64_t* run = M.brun.data() + (size_t)p * ((size_t)k + 1);
                 const int64_t b0 = M.boff[(size_t)p];
                 int32_t gown;
+                E.gradc.cur_p = p;
                 if ((st = acquire(c, E, E.gradc, p, s, true, &gown)) != GNN_OK) return st;
                 E.gradc.slots[(size_t)gown].pinned = true;
                 {
@@ -514,6 +588,13 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
     GNN_HIP(hipStreamSynchronize(E.d2h));
     GNN_HIP(hipMemcpy(loss_out, scal, sizeof(float), hipMemcpyDeviceToHost));
     c->loss_done = true;
+    c->stream_stats.act_loads = E.actc.loads;
+    c->stream_stats.act_hits = E.actc.hits;
+    c->stream_stats.grad_loads = E.gradc.loads;
+    c->stream_stats.grad_hits = E.gradc.hits;
+    c->stream_stats.grad_writebacks = E.gradc.writebacks;
+    c->stream_stats.h2d_bytes = E.h2d_bytes;
+    c->stream_stats.d2h_bytes = E.d2h_bytes;
     return check_launch(c, "gnn_epoch (streaming)");
 }
 
