@@ -142,6 +142,181 @@ def assign_random_fast(n: int, k: int, seed: int) -> np.ndarray:
 
 
 # ----------------------------------------------------------------------------------------
+# switching-aware partitioner, complete procedure (partitioning section; appendix "Insights
+# and Details" of the partitioner; convergence table in the appendix)
+# ----------------------------------------------------------------------------------------
+FRAC_ONE = 1 << 20          # fixed-point scale of #N(v,j)/#N(v,.) in the exact objective
+
+
+def switching_preferences(nb_parts, cur: int, n: int, k: int, sizes):
+    """First and second preference of a vertex whose neighbours lie in ``nb_parts``.
+
+    The partitions a vertex can prefer are those that occur among its neighbours, plus the
+    one it is in.  They are ranked by the paper's score ``1 + #N(v,j)/#N(v,.) - Penalty_j``
+    in the exact integer form used by :func:`lp_targets`; equal scores rank the current
+    partition first, then the lower id.  The second preference is ``-1`` when only one
+    partition can be preferred."""
+    nb_parts = np.asarray(nb_parts, dtype=np.int64)
+    deg = len(nb_parts)
+    cnt = np.bincount(nb_parts, minlength=k)
+    domain = sorted(set(int(j) for j in nb_parts) | {int(cur)})
+    ranked = sorted(domain, key=lambda j: (-(11 * n * int(cnt[j]) - 10 * k * deg * int(sizes[j])),
+                                           0 if j == cur else 1, j))
+    return ranked[0], (ranked[1] if len(ranked) > 1 else -1)
+
+
+def switching_objective(rowptr, colidx, part, k: int) -> int:
+    """The partitioner's objective ``sum_v Score(v, partition_v)`` as an exact integer:
+    ``11 |V| * sum_v (2^20 + floor(2^20 #N(v,p_v) / #N(v,.))) - 10 k 2^20 sum_j |P_j|^2``
+    (the score times ``11 |V| 2^20``, the neighbour fraction rounded down to 20 fractional
+    bits and taken as 0 for a vertex without neighbours)."""
+    n = len(rowptr) - 1
+    sizes = np.bincount(part, minlength=k)
+    total = 0
+    for v in range(n):
+        nb = colidx[rowptr[v]:rowptr[v + 1]]
+        nb = nb[nb != v]
+        frac = 0
+        if len(nb):
+            frac = (FRAC_ONE * int(np.count_nonzero(part[nb] == part[v]))) // len(nb)
+        total += FRAC_ONE + frac
+    return 11 * n * total - 10 * k * FRAC_ONE * sum(int(x) * int(x) for x in sizes)
+
+
+def worker_capacity(rc: int, workers: int, w: int) -> int:
+    """Share of a partition's relocation capacity ``rc`` given to worker ``w``: an equal
+    split, the remainder going to the first workers."""
+    return rc // workers + (1 if w < rc % workers else 0)
+
+
+def switching_iteration(rowptr, colidx, part, k: int, workers: int):
+    """One iteration from the frozen state ``part``; returns the new assignment.
+
+    Relocation capacity of partition ``j``: ``RC_j = floor(1.1 |V| / k) - |P_j|`` (not below
+    zero).  The vertices are split into ``workers`` contiguous ranges
+    ``[floor(w |V| / W), floor((w+1) |V| / W))``; each worker keeps, per partition ``j``, the
+    list of its vertices whose first preference is ``j`` and differs from where they are,
+    groups that list by second preference, and relocates the largest group (ties: the lower
+    second preference, "none" lowest) in ascending vertex id, at most its share of ``RC_j``."""
+    n = len(rowptr) - 1
+    part = np.asarray(part, dtype=np.int32)
+    sizes = np.bincount(part, minlength=k).astype(np.int64)
+    cap = (11 * n) // (10 * k)
+    new = part.copy()
+    for w in range(workers):
+        lo, hi = (w * n) // workers, ((w + 1) * n) // workers
+        lists = [dict() for _ in range(k)]          # per target partition: second pref -> vertices
+        for v in range(lo, hi):
+            nb = colidx[rowptr[v]:rowptr[v + 1]]
+            nb = nb[nb != v]
+            first, second = switching_preferences(part[nb], int(part[v]), n, k, sizes)
+            if first != part[v]:
+                lists[first].setdefault(second, []).append(v)
+        for j in range(k):
+            if not lists[j]:
+                continue
+            room = worker_capacity(max(0, cap - int(sizes[j])), workers, w)
+            g = min(lists[j], key=lambda sec: (-len(lists[j][sec]), sec))
+            for v in lists[j][g][:room]:
+                new[v] = j
+    return new
+
+
+def assign_switching(rowptr, colidx, k: int, seed: int, workers: int = 8, max_iters: int = 50,
+                     window: int = 5, iteration=None, objective=None):
+    """The complete partitioner: random start, iterations of :func:`switching_iteration`,
+    halting when the objective has improved by less than 0.1 % of its previous value in
+    ``window`` consecutive iterations, after ``max_iters`` iterations at the latest.
+    Returns the assignment and the list of objective values (initial state first)."""
+    iteration = iteration or switching_iteration
+    objective = objective or switching_objective
+    n = len(rowptr) - 1
+    part = assign_random(n, k, seed) if n < 200_000 else assign_random_fast(n, k, seed)
+    hist = [objective(rowptr, colidx, part, k)]
+    streak = 0
+    for _ in range(max_iters):
+        part = iteration(rowptr, colidx, part, k, workers)
+        hist.append(objective(rowptr, colidx, part, k))
+        small = 1000 * (hist[-1] - hist[-2]) < abs(hist[-2])
+        streak = streak + 1 if small else 0
+        if streak == window:
+            break
+    return part, hist
+
+
+def _count_table(rowptr, colidx, part, k):
+    n = len(rowptr) - 1
+    rows = np.repeat(np.arange(n, dtype=np.int64), np.diff(rowptr))
+    cols = np.asarray(colidx, dtype=np.int64)
+    keep = rows != cols
+    rows, cols = rows[keep], cols[keep]
+    return np.bincount(rows * k + part[cols], minlength=n * k).reshape(n, k).astype(np.int64)
+
+
+def switching_iteration_fast(rowptr, colidx, part, k: int, workers: int):
+    """Same result as :func:`switching_iteration` with a dense ``[n, k]`` count table."""
+    n = len(rowptr) - 1
+    part = np.asarray(part, dtype=np.int32)
+    cur = part.astype(np.int64)
+    sizes = np.bincount(part, minlength=k).astype(np.int64)
+    cnt = _count_table(rowptr, colidx, part, k)
+    deg = cnt.sum(axis=1)
+    ar = np.arange(n)
+    key = 11 * n * cnt - 10 * k * deg[:, None] * sizes[None, :]
+    allowed = cnt > 0
+    allowed[ar, cur] = True
+    # rank by (key desc, current first, id asc): fold the tie-breaks into one sortable value
+    lowest = key.min() - 1
+    keyd = np.where(allowed, key, lowest)
+    def best(keyd):
+        m = keyd.max(axis=1)
+        tie = keyd == m[:, None]
+        pick = np.argmax(tie, axis=1)
+        return np.where(tie[ar, cur], cur, pick), m
+    first, _ = best(keyd)
+    keyd2 = keyd.copy()
+    keyd2[ar, first] = lowest
+    allowed2 = allowed.copy()
+    allowed2[ar, first] = False
+    second, _ = best(keyd2)
+    second = np.where(allowed2.any(axis=1), second, -1)
+    cap = (11 * n) // (10 * k)
+    new = part.copy()
+    cand = np.flatnonzero(first != cur)
+    wk = np.searchsorted(np.array([(w * n) // workers for w in range(1, workers + 1)]), cand, side="right")
+    order = np.lexsort((cand, second[cand], first[cand], wk))
+    cand = cand[order]
+    grp = np.stack([wk[order], first[cand], second[cand]], axis=1)
+    if len(cand) == 0:
+        return new
+    change = np.flatnonzero(np.any(grp[1:] != grp[:-1], axis=1)) + 1
+    starts = np.concatenate([[0], change])
+    ends = np.concatenate([change, [len(cand)]])
+    bestg = {}
+    for s0, e0 in zip(starts, ends):
+        w, j, sec = (int(x) for x in grp[s0])
+        b = bestg.get((w, j))
+        if b is None or (e0 - s0) > b[0]:           # groups arrive in ascending `sec`
+            bestg[(w, j)] = (e0 - s0, s0)
+    for (w, j), (length, s0) in bestg.items():
+        room = worker_capacity(max(0, cap - int(sizes[j])), workers, w)
+        new[cand[s0:s0 + min(length, room)]] = j
+    return new
+
+
+def switching_objective_fast(rowptr, colidx, part, k: int) -> int:
+    n = len(rowptr) - 1
+    part = np.asarray(part, dtype=np.int32)
+    cnt = _count_table(rowptr, colidx, part, k)
+    deg = cnt.sum(axis=1)
+    same = cnt[np.arange(n), part.astype(np.int64)]
+    frac = np.where(deg > 0, (FRAC_ONE * same) // np.maximum(deg, 1), 0)
+    total = int(n) * FRAC_ONE + int(frac.sum())
+    sizes = np.bincount(part, minlength=k)
+    return 11 * n * total - 10 * k * FRAC_ONE * sum(int(x) * int(x) for x in sizes)
+
+
+# ----------------------------------------------------------------------------------------
 # partition structure by set arithmetic
 # ----------------------------------------------------------------------------------------
 def owned(part, p: int) -> np.ndarray:

@@ -8,7 +8,7 @@ import pytest
 from helpers import random_weights, small_graph
 from oracle import fullgraph as og
 from oracle import partition as op
-from synth import csr_from_edges
+from synth import csr_from_edges, make_config
 
 GOLD = os.path.join(os.path.dirname(__file__), "golden")
 
@@ -171,3 +171,140 @@ def test_partitionwise_equals_full_graph_for_any_k(model, gkw):
         for key in ("act", "gW", "gb", "gact") + (("gWs",) if model == "sage" else ()):
             for a, b in zip(pw[key], full[key]):
                 assert np.abs(a - b).max() < 1e-12, (key, k)
+
+
+# ----------------------------------------------------------------------------------------
+# the complete switching-aware partitioner
+# ----------------------------------------------------------------------------------------
+def _read_group_example():
+    path = os.path.join(os.path.dirname(__file__), "golden", "switching_group_example.txt")
+    fx = {"rows": {}, "first": {}, "second": {}}
+    for line in open(path):
+        if line.startswith("#") or not line.strip():
+            continue
+        key, *vals = line.split()
+        vals = [int(x) for x in vals]
+        if key == "row":
+            fx["rows"][vals[0]] = vals[1:]
+        elif key == "first_preference":
+            fx["first"][vals[0]] = vals[1]
+        elif key == "second_preference":
+            fx["second"][vals[0]] = vals[1]
+        else:
+            fx[key] = vals
+    return fx
+
+
+def test_switching_group_example_from_the_paper():
+    fx = _read_group_example()
+    n, k = fx["n"][0], fx["k"][0]
+    part = np.full(n, -1, dtype=np.int32)
+    for j in range(k):
+        part[fx["partition%d" % j]] = j
+    assert part.min() >= 0
+    rowptr = np.zeros(n + 1, dtype=np.int64)
+    cols = []
+    for v in range(n):
+        cols += sorted(fx["rows"].get(v, []))
+        rowptr[v + 1] = len(cols)
+    colidx = np.array(cols, dtype=np.int32)
+    sizes = np.bincount(part, minlength=k)
+    for v in fx["candidates_of_partition2"]:
+        nb = colidx[rowptr[v]:rowptr[v + 1]]
+        first, second = op.switching_preferences(part[nb], int(part[v]), n, k, sizes)
+        assert (first, second) == (fx["first"][v], fx["second"][v]), v
+    for workers in (1, 2):      # with two ranges vertices 0, 6, 8 are still in the same one
+        new = op.switching_iteration(rowptr, colidx, part, k, workers)
+        moved = np.flatnonzero(new != part)
+        assert list(moved) == fx["relocated_to_partition2"]
+        assert np.all(new[moved] == 2)
+    assert np.array_equal(op.switching_iteration_fast(rowptr, colidx, part, k, 1), new)
+
+
+def _random_graph(n, m, seed, symmetric=True):
+    rng = np.random.default_rng(seed)
+    src = rng.integers(0, n, m)
+    dst = (src + 1 + rng.zipf(1.6, m) % (n - 1)) % n
+    if symmetric:
+        src, dst = np.concatenate([src, dst]), np.concatenate([dst, src])
+    key = np.unique(dst.astype(np.int64) * n + src)
+    rows, cols = key // n, key % n
+    rowptr = np.zeros(n + 1, dtype=np.int64)
+    np.add.at(rowptr, rows + 1, 1)
+    return np.cumsum(rowptr), cols.astype(np.int32)
+
+
+@pytest.mark.parametrize("n,m,k,workers", [(300, 1500, 5, 3), (257, 900, 9, 16), (64, 400, 2, 1)])
+def test_switching_vectorised_equals_loop_and_keeps_the_capacity(n, m, k, workers):
+    rowptr, colidx = _random_graph(n, m, seed=n + k)
+    part = op.assign_random(n, k, 3)
+    cap = (11 * n) // (10 * k)
+    for it in range(6):
+        assert op.switching_objective(rowptr, colidx, part, k) == \
+            op.switching_objective_fast(rowptr, colidx, part, k)
+        new = op.switching_iteration(rowptr, colidx, part, k, workers)
+        assert np.array_equal(new, op.switching_iteration_fast(rowptr, colidx, part, k, workers))
+        sizes, new_sizes = np.bincount(part, minlength=k), np.bincount(new, minlength=k)
+        assert new_sizes.max() <= max(cap, sizes.max())
+        # no range sends a partition more vertices than its share of the relocation capacity
+        for w in range(workers):
+            lo, hi = (w * n) // workers, ((w + 1) * n) // workers
+            into = np.bincount(new[lo:hi][new[lo:hi] != part[lo:hi]], minlength=k)
+            for j in range(k):
+                assert into[j] <= op.worker_capacity(max(0, cap - int(sizes[j])), workers, w)
+        part = new
+
+
+def test_switching_objective_is_the_papers_sum_of_scores():
+    n, k = 200, 4
+    rowptr, colidx = _random_graph(n, 1200, seed=9)
+    part = op.assign_random(n, k, 1)
+    part[:30] = 0                                   # unbalanced on purpose: the penalty matters
+    sizes = np.bincount(part, minlength=k)
+    total = 0.0
+    for v in range(n):
+        nb = colidx[rowptr[v]:rowptr[v + 1]]
+        nb = nb[nb != v]
+        frac = np.mean(part[nb] == part[v]) if len(nb) else 0.0
+        total += 1.0 + frac - sizes[part[v]] / (1.1 * n / k)
+    exact = op.switching_objective(rowptr, colidx, part, k) / (11 * n * op.FRAC_ONE)
+    assert abs(exact - total) <= n * 2.0 ** -20 + 1e-9 * abs(total)
+
+
+def test_switching_halts_on_five_small_improvements_in_a_row_or_after_fifty():
+    rowptr, colidx = _random_graph(40, 100, seed=2)
+    def run(values):
+        seq = iter(values)
+        part, hist = op.assign_switching(rowptr, colidx, 2, 0, workers=1,
+                                         iteration=lambda rp, ci, p, k, w: p,
+                                         objective=lambda rp, ci, p, k: next(seq))
+        return len(hist) - 1
+    big = [1000 * 2 ** i for i in range(60)]
+    assert run(big) == 50                                        # never converges: the cap
+    flat = [1000000] * 60
+    assert run(flat) == 5                                        # five small steps from the start
+    # an improvement of exactly 0.1 % of the previous value still counts as an improvement
+    def chain(step):
+        v = [1000000]
+        for _ in range(60):
+            v.append(v[-1] + step(v[-1]))
+        return v
+    assert run(chain(lambda prev: -(-prev // 1000))) == 50
+    assert run(chain(lambda prev: -(-prev // 1000) - 1)) == 5
+    # a real improvement resets the count; a loss counts as "no improvement"
+    seq = [1000, 2000, 2001, 2001, 1990, 1990, 3000, 3001, 3001, 3001, 3001, 3001, 9999]
+    assert run(seq + [9999] * 50) == 11
+
+
+def test_switching_improves_the_expansion_ratio_of_a_power_law_graph():
+    cfg, rowptr, colidx = make_config("tiny")
+    n, k = cfg["n"], 4
+    rnd = op.assign_random(n, k, 5)
+    part, hist = op.assign_switching(rowptr, colidx, k, 5, workers=16,
+                                     iteration=op.switching_iteration_fast,
+                                     objective=op.switching_objective_fast)
+    assert len(hist) - 1 <= 50 and hist[-1] > hist[0]
+    assert np.bincount(part, minlength=k).max() <= (11 * n) // (10 * k)
+    a0 = op.alpha(rowptr, colidx, rnd, k, self_loops=True)
+    a1 = op.alpha(rowptr, colidx, part, k, self_loops=True)
+    assert a1 < 0.97 * a0, (a0, a1)
