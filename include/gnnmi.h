@@ -49,7 +49,12 @@ typedef enum {
 
 typedef enum { GNN_GCN = 0, GNN_SAGE_MEAN = 1 } gnn_model;
 typedef enum { GNN_F32 = 0, GNN_BF16 = 1 } gnn_dtype; /* storage type of activations/weights */
-typedef enum { GNN_PART_USER = 0, GNN_PART_RANDOM = 1, GNN_PART_LP = 2 } gnn_part_mode;
+typedef enum {
+    GNN_PART_USER = 0,
+    GNN_PART_RANDOM = 1,
+    GNN_PART_LP = 2,
+    GNN_PART_SWITCHING = 3
+} gnn_part_mode;
 
 typedef struct {
     int32_t model;            /* gnn_model */
@@ -118,7 +123,15 @@ const char *gnn_last_error(const gnn_ctx *ctx);
  *     vertices by (splitmix64(seed ^ splitmix64(v)), v) and deals ranks round-robin;
  *     GNN_PART_LP runs 10 synchronous rounds of first-preference label propagation with the
  *     paper's size penalty (balance factor 1.1) and capacity floor(1.1 n / k), starting
- *     from GNN_PART_RANDOM (partitioning section and its appendix).
+ *     from GNN_PART_RANDOM (partitioning section and its appendix);
+ *     GNN_PART_SWITCHING is the complete switching-aware partitioner (same passages): from
+ *     GNN_PART_RANDOM, per iteration every vertex takes a first and a second preference by
+ *     that score among the partitions of its neighbours and its own, the vertices are cut
+ *     into 16 contiguous ranges, and in each range, per target partition, the largest group
+ *     of candidates sharing a second preference relocates, limited to the range's share of
+ *     the relocation capacity floor(1.1 n / k) - |P_j|; it halts when the objective (the
+ *     sum of the vertices' scores, evaluated exactly) has improved by less than 0.1 % in 5
+ *     consecutive iterations, or after 50.  Deterministic for a given (graph, k, seed).
  * Errors: GNN_EINVAL (null, n < 1, k < 1, k > n, malformed CSR, bad user_part),
  * GNN_ENOMEM.  May be called again to repartition; a bound context becomes unbound. */
 gnn_status gnn_build_partitions(gnn_ctx *ctx, int64_t n, const int64_t *rowptr,
@@ -132,6 +145,11 @@ gnn_status gnn_get_order(const gnn_ctx *ctx, const int32_t **order /* n: origina
                          const int64_t **part_offset /* k+1: first row of each partition */);
 gnn_status gnn_get_boundary(const gnn_ctx *ctx, int32_t p, const int32_t **idx, int64_t *count);
 gnn_status gnn_get_stats(const gnn_ctx *ctx, gnn_stats *out);
+/* GNN_PART_SWITCHING only (0 iterations otherwise): iterations run and, in objective[i] for
+ * i <= iterations, the mean score per vertex of the state after i iterations (convergence
+ * table in the appendix).  At most `capacity` values are written. */
+gnn_status gnn_get_partitioner_history(const gnn_ctx *ctx, int32_t *iterations, double *objective,
+                                       int32_t capacity);
 
 /* Bytes the caller must provide as `staging` (largest |B_p| rows of the widest gathered
  * layer) and `scratch` (per-partition intermediates: aggregate Z_p, dY_p, dZ_p, gradient of

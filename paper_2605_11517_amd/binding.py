@@ -13,13 +13,14 @@ import numpy as np
 
 GNN_GCN, GNN_SAGE_MEAN = 0, 1
 GNN_F32, GNN_BF16 = 0, 1
-GNN_PART_USER, GNN_PART_RANDOM, GNN_PART_LP = 0, 1, 2
+GNN_PART_USER, GNN_PART_RANDOM, GNN_PART_LP, GNN_PART_SWITCHING = 0, 1, 2, 3
 KERNEL_CLASSES = ("gather", "spmm", "gemm_fwd", "loss", "act_bwd", "gemm_dw", "gemm_dz",
                   "spmm_t", "scatter", "other", "spmm_reduce")
 STATUS = {0: "GNN_OK", 1: "GNN_EINVAL", 2: "GNN_ENOMEM", 3: "GNN_EHIP", 4: "GNN_ESTATE",
           5: "GNN_EUNSUPPORTED"}
 _MODEL = {"gcn": GNN_GCN, "sage": GNN_SAGE_MEAN}
-_PART = {"user": GNN_PART_USER, "random": GNN_PART_RANDOM, "lp": GNN_PART_LP}
+_PART = {"user": GNN_PART_USER, "random": GNN_PART_RANDOM, "lp": GNN_PART_LP,
+         "switching": GNN_PART_SWITCHING}
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libgnnmi.so")
 _lib = None
@@ -80,6 +81,7 @@ def load_library():
         "gnn_set_profiling": [vp, i32],
         "gnn_get_profile": [vp, P(C.c_double), P(i64)],
         "gnn_get_stream_stats": [vp, P(StreamStats)],
+        "gnn_get_partitioner_history": [vp, P(i32), P(C.c_double), i32],
     }
     for name, args in sig.items():
         fn = getattr(lib, name)
@@ -169,6 +171,12 @@ class Context:
         s = _Stats()
         self._check(self.lib.gnn_get_stats(self.h, C.byref(s)))
         return {f: getattr(s, f) for f, _ in _Stats._fields_}
+
+    def get_partitioner_history(self):
+        it = C.c_int32()
+        obj = (C.c_double * 64)()
+        self._check(self.lib.gnn_get_partitioner_history(self.h, C.byref(it), obj, 64))
+        return int(it.value), [float(obj[i]) for i in range(min(it.value + 1, 64))]
 
     def workspace_bytes(self):
         a, b = C.c_int64(), C.c_int64()

@@ -448,6 +448,17 @@ gnn_status gnn_get_stats(const gnn_ctx* c, gnn_stats* out)
     return GNN_OK;
 }
 
+gnn_status gnn_get_partitioner_history(const gnn_ctx* c, int32_t* iterations, double* objective,
+                                       int32_t capacity)
+{
+    if (!c || !iterations || (capacity > 0 && !objective)) return GNN_EINVAL;
+    if (!c->built) return c->fail(GNN_ESTATE, "no partitions built");
+    *iterations = c->M.part_iterations;
+    const int64_t m = std::min<int64_t>(capacity, (int64_t)c->M.part_objective.size());
+    for (int64_t i = 0; i < m; ++i) objective[i] = c->M.part_objective[(size_t)i];
+    return GNN_OK;
+}
+
 gnn_status gnn_workspace_bytes(const gnn_ctx* c, int64_t* staging, int64_t* scratch)
 {
     if (!c || !staging || !scratch) return GNN_EINVAL;

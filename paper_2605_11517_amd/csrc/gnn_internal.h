@@ -40,6 +40,8 @@ struct HostMeta {
     std::vector<int32_t> tcol;      // local destination row (0 .. n_p)
     std::vector<float> tw;          // weight of the entry (both models)
     gnn_stats stats{};
+    int32_t part_iterations = 0;          // switching-aware partitioner: iterations run
+    std::vector<double> part_objective;   // and the mean score per vertex of every state
     // work decomposition of the aggregation kernels (forward operator and its transpose)
     struct Plan {
         std::vector<int64_t> range_off;   // k+1, offsets into range_rows (partition p has

@@ -137,6 +137,160 @@ void lp_round(int64_t n, const int64_t* rowptr, const int32_t* colidx, int32_t k
     }
 }
 
+// ---- the complete switching-aware partitioner (partitioning section; appendix with its
+// insights and details) ------------------------------------------------------------------
+//
+// One iteration, from the frozen state S_i:
+//   1. source-level parallelism: every vertex ranks the partitions that occur among its
+//      neighbours, plus its own, by the score 1 + #N(v,j)/#N(v,.) - |P_j|/(1.1 |V|/k) (as the
+//      exact integer key 11 |V| #N(v,j) - 10 k #N(v,.) |P_j|; equal keys: own partition first,
+//      then the lower id) and keeps the first and the second preference;
+//   2. the vertices are split into kSwitchingWorkers contiguous ranges.  Each range keeps, per
+//      partition j, its candidates (first preference j, currently elsewhere), groups them by
+//      second preference and relocates the largest group (ties: lower second preference, "none"
+//      lowest) in ascending vertex id, at most its share of the relocation capacity
+//      RC_j = floor(1.1 |V|/k) - |P_j| (equal split, remainder to the first ranges);
+//   3. the objective sum_v Score(v, partition_v) of the new state is evaluated exactly (scaled
+//      by 11 |V| 2^20, neighbour fraction rounded down to 20 bits); the loop halts when it has
+//      improved by less than 0.1 % of its previous value in 5 consecutive iterations, or after
+//      50 iterations.
+// The number of ranges is a constant of the rule, not the number of threads, so the result
+// does not depend on the machine.  The paper's "Dst's Partition" mirror of the adjacency is
+// not materialised: the assignment array it would cache is itself cache-resident here.
+constexpr int32_t kSwitchingWorkers = 16;
+constexpr int32_t kSwitchingMaxIters = 50;
+constexpr int32_t kSwitchingWindow = 5;
+constexpr int64_t kFracOne = 1 << 20;
+
+struct SwitchingInfo {
+    int32_t iterations = 0;
+    std::vector<double> objective;   // mean score per vertex, initial state first
+};
+
+void assign_switching(int64_t n, const int64_t* rowptr, const int32_t* colidx, int32_t k,
+                      uint64_t seed, std::vector<int32_t>& part, SwitchingInfo& info)
+{
+    assign_random(n, k, seed, part);
+    const int nt = worker_count();
+    const int64_t cap = ((int64_t)11 * n) / ((int64_t)10 * k);
+    std::vector<int32_t> first((size_t)n), second((size_t)n);
+    std::vector<int64_t> sizes((size_t)k);
+    std::vector<std::vector<int64_t>> cnt((size_t)nt, std::vector<int64_t>((size_t)k, 0));
+    std::vector<std::vector<int32_t>> touched((size_t)nt);
+    constexpr int64_t kChunk = 4096;
+    const int64_t nchunks = (n + kChunk - 1) / kChunk;
+    std::vector<int64_t> frac_sum((size_t)nchunks);
+    struct Cand { int32_t first, second, v; };
+    std::vector<std::vector<Cand>> cands((size_t)kSwitchingWorkers);
+    __int128 prev_q = 0;
+    int32_t streak = 0;
+
+    for (int32_t it = 0;; ++it) {
+        std::fill(sizes.begin(), sizes.end(), 0);
+        for (int64_t v = 0; v < n; ++v) sizes[(size_t)part[(size_t)v]]++;
+        // step 1 on the current state, together with the objective of that state
+        parallel_for(nchunks, 1, [&](int tid, int64_t ch) {
+            auto& c = cnt[(size_t)tid];
+            auto& tl = touched[(size_t)tid];
+            int64_t fsum = 0;
+            const int64_t hi = std::min(n, (ch + 1) * kChunk);
+            for (int64_t v = ch * kChunk; v < hi; ++v) {
+                tl.clear();
+                int64_t deg = 0;
+                for (int64_t e = rowptr[v]; e < rowptr[v + 1]; ++e) {
+                    const int32_t u = colidx[e];
+                    if (u == v) continue;
+                    const int32_t j = part[(size_t)u];
+                    if (c[(size_t)j]++ == 0) tl.push_back(j);
+                    ++deg;
+                }
+                const int32_t cur = part[(size_t)v];
+                if (deg > 0) fsum += kFracOne * c[(size_t)cur] / deg;
+                if (c[(size_t)cur] == 0) tl.push_back(cur);
+                auto key = [&](int32_t j) {
+                    return (int64_t)11 * n * c[(size_t)j] - (int64_t)10 * k * deg * sizes[(size_t)j];
+                };
+                // better(a, b): a ranks before b
+                auto better = [&](int32_t a, int64_t ka, int32_t b, int64_t kb) {
+                    if (ka != kb) return ka > kb;
+                    if ((a == cur) != (b == cur)) return a == cur;
+                    return a < b;
+                };
+                int32_t b1 = -1, b2 = -1;
+                int64_t k1 = 0, k2 = 0;
+                for (int32_t j : tl) {
+                    const int64_t kj = key(j);
+                    if (b1 < 0 || better(j, kj, b1, k1)) {
+                        b2 = b1; k2 = k1;
+                        b1 = j; k1 = kj;
+                    } else if (b2 < 0 || better(j, kj, b2, k2)) {
+                        b2 = j; k2 = kj;
+                    }
+                }
+                first[(size_t)v] = b1;
+                second[(size_t)v] = b2;
+                for (int32_t j : tl) c[(size_t)j] = 0;
+            }
+            frac_sum[(size_t)ch] = fsum;
+        });
+        __int128 total = (__int128)n * kFracOne;
+        for (int64_t ch = 0; ch < nchunks; ++ch) total += frac_sum[(size_t)ch];
+        __int128 sq = 0;
+        for (int32_t j = 0; j < k; ++j) sq += (__int128)sizes[(size_t)j] * sizes[(size_t)j];
+        const __int128 q = (__int128)11 * n * total - (__int128)10 * k * kFracOne * sq;
+        info.objective.push_back((double)q / ((double)11 * (double)n * (double)kFracOne * (double)n));
+        if (it > 0) {
+            const __int128 mag = prev_q < 0 ? -prev_q : prev_q;
+            const bool small = (__int128)1000 * (q - prev_q) < mag;
+            streak = small ? streak + 1 : 0;
+        }
+        prev_q = q;
+        info.iterations = it;
+        if (streak == kSwitchingWindow || it == kSwitchingMaxIters) break;
+
+        // step 2: per range, per target partition, the largest second-preference group moves
+        std::atomic<int64_t> moved{0};
+        parallel_for(kSwitchingWorkers, 1, [&](int, int64_t w) {
+            auto& L = cands[(size_t)w];
+            L.clear();
+            const int64_t lo = (w * n) / kSwitchingWorkers, hi = ((w + 1) * n) / kSwitchingWorkers;
+            for (int64_t v = lo; v < hi; ++v)
+                if (first[(size_t)v] != part[(size_t)v])
+                    L.push_back({first[(size_t)v], second[(size_t)v], (int32_t)v});
+            std::sort(L.begin(), L.end(), [](const Cand& a, const Cand& b) {
+                if (a.first != b.first) return a.first < b.first;
+                if (a.second != b.second) return a.second < b.second;
+                return a.v < b.v;
+            });
+            int64_t local_moved = 0;
+            size_t i = 0;
+            while (i < L.size()) {
+                const int32_t j = L[i].first;
+                size_t best_lo = i, best_len = 0;
+                size_t g = i;
+                while (g < L.size() && L[g].first == j) {
+                    size_t e = g;
+                    while (e < L.size() && L[e].first == j && L[e].second == L[g].second) ++e;
+                    if (e - g > best_len) { best_len = e - g; best_lo = g; }   // ascending second: first wins ties
+                    g = e;
+                }
+                const int64_t rc = std::max<int64_t>(0, cap - sizes[(size_t)j]);
+                const int64_t room = rc / kSwitchingWorkers + (w < rc % kSwitchingWorkers ? 1 : 0);
+                const size_t take = (size_t)std::min<int64_t>((int64_t)best_len, room);
+                // first[] of a mover is its new home; the assignment itself changes below
+                for (size_t t = best_lo; t < best_lo + take; ++t) second[(size_t)L[t].v] = -2;
+                local_moved += (int64_t)take;
+                i = g;
+            }
+            moved += local_moved;
+        });
+        if (moved.load() == 0) break;   // a fixed point: every further iteration repeats it
+        parallel_for(n, 1 << 16, [&](int, int64_t v) {
+            if (second[(size_t)v] == -2) part[(size_t)v] = first[(size_t)v];
+        });
+    }
+}
+
 // Cuts the rows [0, nrows) of one partition (row pointers rp[0..nrows], absolute positions)
 // into work items: rows longer than kSpmmSegment become segments of that many entries; the
 // others are grouped into consecutive ranges holding at most kSpmmSegment entries and
@@ -221,7 +375,8 @@ gnn_status build_host_meta(int model, int64_t n, const int64_t* rowptr, const in
     if (!rowptr || n < 1) { err = "n must be >= 1 and rowptr non-null"; return GNN_EINVAL; }
     if (n > 0x7FFFFFF0ll) { err = "n exceeds the int32 vertex id range"; return GNN_EINVAL; }
     if (k < 1 || (int64_t)k > n) { err = "k must satisfy 1 <= k <= n"; return GNN_EINVAL; }
-    if (mode != GNN_PART_USER && mode != GNN_PART_RANDOM && mode != GNN_PART_LP) {
+    if (mode != GNN_PART_USER && mode != GNN_PART_RANDOM && mode != GNN_PART_LP &&
+        mode != GNN_PART_SWITCHING) {
         err = "unknown partition mode"; return GNN_EINVAL;
     }
     if (mode == GNN_PART_USER && !user_part) { err = "user_part is null"; return GNN_EINVAL; }
@@ -260,6 +415,11 @@ gnn_status build_host_meta(int model, int64_t n, const int64_t* rowptr, const in
                     err = "user_part entry outside [0, k)";
                     return GNN_EINVAL;
                 }
+        } else if (mode == GNN_PART_SWITCHING) {
+            SwitchingInfo info;
+            assign_switching(n, rowptr, colidx, k, seed, M.part, info);
+            M.part_iterations = info.iterations;
+            M.part_objective = std::move(info.objective);
         } else {
             assign_random(n, k, seed, M.part);
             if (mode == GNN_PART_LP)

@@ -69,6 +69,24 @@ def test_epoch_matches_oracle(name):
     assert np.array_equal(part, want)
 
 
+def test_epoch_on_switching_aware_partitions():
+    say("case epoch on switching-aware partitions")
+    cfg, rowptr, colidx = make_config("mini_sage")
+    n, k = cfg["n"], 6
+    X, y, m, w = make_inputs(cfg, n)
+    ref = og.epoch(cfg["model"], rowptr, colidx, cfg["dims"], X, w, y, m)
+    s, loss = run_session(cfg, rowptr, colidx, X, y, m, w, k, "switching", cfg["seed"])
+    assert abs(loss - ref["loss"]) <= TOL * abs(ref["loss"])
+    compare(s.results(), ref, cfg["model"], tag="switching")
+    part, _ = s.ctx.get_partition()
+    want, _ = op.assign_switching(rowptr, colidx, k, cfg["seed"], workers=16,
+                                  iteration=op.switching_iteration_fast,
+                                  objective=op.switching_objective_fast)
+    assert np.array_equal(part, want)
+    for p in range(k):
+        assert np.array_equal(s.ctx.get_boundary(p), op.boundary(rowptr, colidx, want, p))
+
+
 @pytest.mark.parametrize("name", ["tiny", "mini_sage"])
 def test_gathered_rows_are_bit_exact(name):
     say("case gathered_rows %s" % name)

@@ -26,14 +26,29 @@ def test_library_exports_every_declared_symbol():
 
 
 @pytest.mark.parametrize("name,mode", [("tiny", "random"), ("tiny", "lp"), ("mini_sage", "lp"),
-                                       ("mini_gcn_directed", "lp"), ("mini_gcn_directed", "random")])
+                                       ("mini_gcn_directed", "lp"), ("mini_gcn_directed", "random"),
+                                       ("tiny", "switching"), ("mini_sage", "switching"),
+                                       ("mini_gcn_directed", "switching")])
 def test_assignment_and_boundaries_match_oracle(name, mode):
     cfg, rowptr, colidx = make_config(name)
     n, k, seed = cfg["n"], cfg["k"], cfg["seed"]
     ctx = Context(cfg["model"], cfg["dims"])
     ctx.build_partitions(rowptr, colidx, k, mode, seed)
     part, kk = ctx.get_partition()
-    ref = op.assign_random(n, k, seed) if mode == "random" else op.assign_lp(rowptr, colidx, k, seed)
+    if mode == "random":
+        ref = op.assign_random(n, k, seed)
+    elif mode == "lp":
+        ref = op.assign_lp(rowptr, colidx, k, seed)
+    else:
+        # the vectorised oracle functions are checked against the plain loops in
+        # test_oracle_partition.py; the library's rule uses 16 vertex ranges
+        ref, hist = op.assign_switching(rowptr, colidx, k, seed, workers=16,
+                                        iteration=op.switching_iteration_fast,
+                                        objective=op.switching_objective_fast)
+        iters, obj = ctx.get_partitioner_history()
+        assert iters <= len(hist) - 1 <= 50            # the library may stop at a fixed point
+        scale = 11.0 * n * op.FRAC_ONE * n
+        assert np.allclose(obj, [h / scale for h in hist[:iters + 1]], rtol=1e-12, atol=0)
     assert kk == k and part.dtype == np.int32
     assert np.array_equal(part, ref)
     total = 0
@@ -138,3 +153,16 @@ def test_streaming_budget_is_validated():
     ctx = Context("gcn", (4, 3), hbm_budget_bytes=1 << 20)
     ctx.build_partitions(rowptr, colidx, 3, "random")            # builds the per-source runs too
     assert ctx.get_stats()["k"] == 3
+
+
+def test_switching_assignment_does_not_depend_on_the_thread_count(monkeypatch):
+    cfg, rowptr, colidx = make_config("tiny")
+    got = []
+    for threads in ("1", "3", "16"):
+        monkeypatch.setenv("GNNMI_THREADS", threads)
+        ctx = Context(cfg["model"], cfg["dims"])
+        ctx.build_partitions(rowptr, colidx, 6, "switching", 21)
+        got.append(ctx.get_partition()[0].copy())
+    assert np.array_equal(got[0], got[1]) and np.array_equal(got[0], got[2])
+    sizes = np.bincount(got[0], minlength=6)
+    assert sizes.max() <= (11 * cfg["n"]) // (10 * 6)
