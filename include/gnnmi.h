@@ -53,7 +53,8 @@ typedef enum {
     GNN_PART_USER = 0,
     GNN_PART_RANDOM = 1,
     GNN_PART_LP = 2,
-    GNN_PART_SWITCHING = 3
+    GNN_PART_SWITCHING = 3,
+    GNN_PART_SWITCHING_DEVICE = 4
 } gnn_part_mode;
 
 typedef struct {
@@ -132,6 +133,12 @@ const char *gnn_last_error(const gnn_ctx *ctx);
  *     the relocation capacity floor(1.1 n / k) - |P_j|; it halts when the objective (the
  *     sum of the vertices' scores, evaluated exactly) has improved by less than 0.1 % in 5
  *     consecutive iterations, or after 50.  Deterministic for a given (graph, k, seed).
+ *     GNN_PART_SWITCHING_DEVICE is the same rule with the per-vertex preference counting (the
+ *     O(edges) part of every iteration) run as a kernel on the current HIP device; the
+ *     assignment is identical to GNN_PART_SWITCHING.  It copies the CSR to the device for the
+ *     duration of the call (8(n+1) + 4 nnz + 12 n bytes) and supports k <= 4096
+ *     (GNN_EUNSUPPORTED beyond); HIP failures give GNN_EHIP.  Every other mode runs on the
+ *     host alone and needs no device.
  * Errors: GNN_EINVAL (null, n < 1, k < 1, k > n, malformed CSR, bad user_part),
  * GNN_ENOMEM.  May be called again to repartition; a bound context becomes unbound. */
 gnn_status gnn_build_partitions(gnn_ctx *ctx, int64_t n, const int64_t *rowptr,
@@ -145,6 +152,13 @@ gnn_status gnn_get_order(const gnn_ctx *ctx, const int32_t **order /* n: origina
                          const int64_t **part_offset /* k+1: first row of each partition */);
 gnn_status gnn_get_boundary(const gnn_ctx *ctx, int32_t p, const int32_t **idx, int64_t *count);
 gnn_status gnn_get_stats(const gnn_ctx *ctx, gnn_stats *out);
+/* order[t], t < k: the partition gnn_epoch processes at step t of every layer pass.  Step 0
+ * is partition 0; each next step takes the unprocessed partition that shares the most
+ * blocks (its own and the owners of its boundary rows) with the one before, lower id among
+ * equals, so that cached blocks are reused (appendix on I/O optimisations: the next target
+ * is picked statically to exploit already-cached neighbours).  Callers stepping by hand may
+ * use any order; sums over partitions are taken in the order of the calls. */
+gnn_status gnn_get_schedule(const gnn_ctx *ctx, const int32_t **order /* k */);
 /* GNN_PART_SWITCHING only (0 iterations otherwise): iterations run and, in objective[i] for
  * i <= iterations, the mean score per vertex of the state after i iterations (convergence
  * table in the appendix).  At most `capacity` values are written. */

@@ -354,6 +354,23 @@ def alpha(rowptr, colidx, part, k: int, self_loops: bool) -> float:
     return sum(len(required(rowptr, colidx, part, p, self_loops)) for p in range(k)) / n
 
 
+def reuse_order(rowptr, colidx, part, k: int) -> list:
+    """Order in which the partitions are processed so that cached neighbours are reused
+    (appendix on I/O optimisations: the next target partition is picked statically).  The
+    paper gives no rule; this build's reading: start at partition 0, then always take the
+    unprocessed partition with the most blocks (its own and its dependent partitions') in
+    common with the one just processed, the lower id among equals."""
+    deps = [set(dependent_partitions(rowptr, colidx, part, p)) | {p} for p in range(k)]
+    order = [0]
+    left = set(range(1, k))
+    while left:
+        cur = deps[order[-1]]
+        nxt = min(left, key=lambda q: (-len(deps[q] & cur), q))
+        order.append(nxt)
+        left.remove(nxt)
+    return order
+
+
 # ----------------------------------------------------------------------------------------
 # naive partition-wise evaluator (numpy, fp64)
 # ----------------------------------------------------------------------------------------

@@ -14,13 +14,14 @@ import numpy as np
 GNN_GCN, GNN_SAGE_MEAN = 0, 1
 GNN_F32, GNN_BF16 = 0, 1
 GNN_PART_USER, GNN_PART_RANDOM, GNN_PART_LP, GNN_PART_SWITCHING = 0, 1, 2, 3
+GNN_PART_SWITCHING_DEVICE = 4
 KERNEL_CLASSES = ("gather", "spmm", "gemm_fwd", "loss", "act_bwd", "gemm_dw", "gemm_dz",
                   "spmm_t", "scatter", "other", "spmm_reduce")
 STATUS = {0: "GNN_OK", 1: "GNN_EINVAL", 2: "GNN_ENOMEM", 3: "GNN_EHIP", 4: "GNN_ESTATE",
           5: "GNN_EUNSUPPORTED"}
 _MODEL = {"gcn": GNN_GCN, "sage": GNN_SAGE_MEAN}
 _PART = {"user": GNN_PART_USER, "random": GNN_PART_RANDOM, "lp": GNN_PART_LP,
-         "switching": GNN_PART_SWITCHING}
+         "switching": GNN_PART_SWITCHING, "switching_device": GNN_PART_SWITCHING_DEVICE}
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libgnnmi.so")
 _lib = None
@@ -69,6 +70,7 @@ def load_library():
         "gnn_get_order": [vp, P(P(i32)), P(P(i64))],
         "gnn_get_boundary": [vp, i32, P(P(i32)), P(i64)],
         "gnn_get_stats": [vp, P(_Stats)],
+        "gnn_get_schedule": [vp, P(P(i32))],
         "gnn_workspace_bytes": [vp, P(i64), P(i64)],
         "gnn_bind": [vp, vp, P(vp), P(vp), P(vp), P(vp), vp, vp, vp, vp],
         "gnn_permute_rows": [vp, vp, vp, i64, i32, vp],
@@ -171,6 +173,12 @@ class Context:
         s = _Stats()
         self._check(self.lib.gnn_get_stats(self.h, C.byref(s)))
         return {f: getattr(s, f) for f, _ in _Stats._fields_}
+
+    def get_schedule(self):
+        ptr = C.POINTER(C.c_int32)()
+        self._check(self.lib.gnn_get_schedule(self.h, C.byref(ptr)))
+        _, k = self.get_partition()
+        return np.ctypeslib.as_array(ptr, shape=(k,)).copy()
 
     def get_partitioner_history(self):
         it = C.c_int32()

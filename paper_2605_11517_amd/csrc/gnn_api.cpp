@@ -448,6 +448,14 @@ gnn_status gnn_get_stats(const gnn_ctx* c, gnn_stats* out)
     return GNN_OK;
 }
 
+gnn_status gnn_get_schedule(const gnn_ctx* c, const int32_t** order)
+{
+    if (!c || !order) return GNN_EINVAL;
+    if (!c->built) return c->fail(GNN_ESTATE, "no partitions built");
+    *order = c->M.sched.data();
+    return GNN_OK;
+}
+
 gnn_status gnn_get_partitioner_history(const gnn_ctx* c, int32_t* iterations, double* objective,
                                        int32_t capacity)
 {
@@ -658,13 +666,15 @@ gnn_status gnn_epoch(gnn_ctx* c, void* stream, float* loss_out)
     gnn_status st;
     zero_weight_grads(c, s);
     for (int32_t l = 1; l <= L; ++l)
-        for (int32_t p = 0; p < k; ++p) {
+        for (int32_t t = 0; t < k; ++t) {
+            const int32_t p = c->M.sched[(size_t)t];
             if ((st = gnn_gather_boundary(c, l, p, stream)) != GNN_OK) return st;
             if ((st = gnn_layer_fwd(c, l, p, stream)) != GNN_OK) return st;
         }
     if ((st = gnn_loss(c, stream)) != GNN_OK) return st;
     for (int32_t l = L; l >= 1; --l)
-        for (int32_t p = 0; p < k; ++p) {
+        for (int32_t t = 0; t < k; ++t) {
+            const int32_t p = c->M.sched[(size_t)t];
             if ((st = gnn_gather_boundary(c, l, p, stream)) != GNN_OK) return st;
             if ((st = gnn_layer_bwd(c, l, p, stream)) != GNN_OK) return st;
         }

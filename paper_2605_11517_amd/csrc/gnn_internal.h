@@ -39,6 +39,7 @@ struct HostMeta {
     std::vector<int64_t> trp;       // sum |R_p| + 1, positions into tcol / tw
     std::vector<int32_t> tcol;      // local destination row (0 .. n_p)
     std::vector<float> tw;          // weight of the entry (both models)
+    std::vector<int32_t> sched;     // k: order in which an epoch walks the partitions
     gnn_stats stats{};
     int32_t part_iterations = 0;          // switching-aware partitioner: iterations run
     std::vector<double> part_objective;   // and the mean score per vertex of every state
@@ -196,5 +197,13 @@ void launch_loss_finish(const float* partial, int64_t nparts, const unsigned lon
                         float* loss_dev, hipStream_t s);
 
 void launch_fill_zero(void* p, int64_t bytes, hipStream_t s);
+
+// Step 1 of one iteration of the switching-aware partitioner for every vertex: first and second
+// preference (second = -1 if there is none) from the assignment `part` and the partition sizes;
+// *frac_sum += sum over vertices of floor(2^20 #N(v, part v) / #N(v, .)).  k <= switch_pref_max_k().
+int switch_pref_max_k();
+void launch_switch_pref(int64_t n, const int64_t* rowptr, const int32_t* colidx, const int32_t* part,
+                        const int64_t* sizes, int32_t k, int32_t* first, int32_t* second,
+                        unsigned long long* frac_sum, hipStream_t s);
 
 }  // namespace gnnmi

@@ -167,10 +167,49 @@ struct SwitchingInfo {
     std::vector<double> objective;   // mean score per vertex, initial state first
 };
 
+// Device buffers of the device variant of step 1; freed on every path out of the partitioner.
+struct PrefDevice {
+    int64_t* rowptr = nullptr;
+    int32_t* colidx = nullptr;
+    int32_t *part = nullptr, *first = nullptr, *second = nullptr;
+    int64_t* sizes = nullptr;
+    unsigned long long* frac = nullptr;
+    ~PrefDevice()
+    {
+        for (void* p : {(void*)rowptr, (void*)colidx, (void*)part, (void*)first, (void*)second,
+                        (void*)sizes, (void*)frac})
+            if (p) (void)hipFree(p);
+    }
+};
+struct HipFailure {
+    std::string what;
+};
+#define PART_HIP(call)                                                                       \
+    do {                                                                                     \
+        hipError_t e_ = (call);                                                              \
+        if (e_ != hipSuccess) {                                                              \
+            (void)hipGetLastError();                                                         \
+            throw HipFailure{std::string(#call) + ": " + hipGetErrorString(e_)};             \
+        }                                                                                    \
+    } while (0)
+
 void assign_switching(int64_t n, const int64_t* rowptr, const int32_t* colidx, int32_t k,
-                      uint64_t seed, std::vector<int32_t>& part, SwitchingInfo& info)
+                      uint64_t seed, bool on_device, std::vector<int32_t>& part, SwitchingInfo& info)
 {
     assign_random(n, k, seed, part);
+    PrefDevice D;
+    if (on_device) {
+        const int64_t nnz = rowptr[n];
+        PART_HIP(hipMalloc((void**)&D.rowptr, (size_t)(n + 1) * 8));
+        PART_HIP(hipMalloc((void**)&D.colidx, (size_t)std::max<int64_t>(1, nnz) * 4));
+        PART_HIP(hipMalloc((void**)&D.part, (size_t)n * 4));
+        PART_HIP(hipMalloc((void**)&D.first, (size_t)n * 4));
+        PART_HIP(hipMalloc((void**)&D.second, (size_t)n * 4));
+        PART_HIP(hipMalloc((void**)&D.sizes, (size_t)k * 8));
+        PART_HIP(hipMalloc((void**)&D.frac, 8));
+        PART_HIP(hipMemcpy(D.rowptr, rowptr, (size_t)(n + 1) * 8, hipMemcpyHostToDevice));
+        if (nnz > 0) PART_HIP(hipMemcpy(D.colidx, colidx, (size_t)nnz * 4, hipMemcpyHostToDevice));
+    }
     const int nt = worker_count();
     const int64_t cap = ((int64_t)11 * n) / ((int64_t)10 * k);
     std::vector<int32_t> first((size_t)n), second((size_t)n);
@@ -189,6 +228,18 @@ void assign_switching(int64_t n, const int64_t* rowptr, const int32_t* colidx, i
         std::fill(sizes.begin(), sizes.end(), 0);
         for (int64_t v = 0; v < n; ++v) sizes[(size_t)part[(size_t)v]]++;
         // step 1 on the current state, together with the objective of that state
+        unsigned long long device_frac = 0;
+        if (on_device) {
+            PART_HIP(hipMemcpy(D.part, part.data(), (size_t)n * 4, hipMemcpyHostToDevice));
+            PART_HIP(hipMemcpy(D.sizes, sizes.data(), (size_t)k * 8, hipMemcpyHostToDevice));
+            PART_HIP(hipMemset(D.frac, 0, 8));
+            launch_switch_pref(n, D.rowptr, D.colidx, D.part, D.sizes, k, D.first, D.second, D.frac, nullptr);
+            PART_HIP(hipGetLastError());
+            PART_HIP(hipMemcpy(first.data(), D.first, (size_t)n * 4, hipMemcpyDeviceToHost));
+            PART_HIP(hipMemcpy(second.data(), D.second, (size_t)n * 4, hipMemcpyDeviceToHost));
+            PART_HIP(hipMemcpy(&device_frac, D.frac, 8, hipMemcpyDeviceToHost));
+            std::fill(frac_sum.begin(), frac_sum.end(), 0);
+        } else {
         parallel_for(nchunks, 1, [&](int tid, int64_t ch) {
             auto& c = cnt[(size_t)tid];
             auto& tl = touched[(size_t)tid];
@@ -233,7 +284,8 @@ void assign_switching(int64_t n, const int64_t* rowptr, const int32_t* colidx, i
             }
             frac_sum[(size_t)ch] = fsum;
         });
-        __int128 total = (__int128)n * kFracOne;
+        }
+        __int128 total = (__int128)n * kFracOne + device_frac;
         for (int64_t ch = 0; ch < nchunks; ++ch) total += frac_sum[(size_t)ch];
         __int128 sq = 0;
         for (int32_t j = 0; j < k; ++j) sq += (__int128)sizes[(size_t)j] * sizes[(size_t)j];
@@ -376,7 +428,7 @@ gnn_status build_host_meta(int model, int64_t n, const int64_t* rowptr, const in
     if (n > 0x7FFFFFF0ll) { err = "n exceeds the int32 vertex id range"; return GNN_EINVAL; }
     if (k < 1 || (int64_t)k > n) { err = "k must satisfy 1 <= k <= n"; return GNN_EINVAL; }
     if (mode != GNN_PART_USER && mode != GNN_PART_RANDOM && mode != GNN_PART_LP &&
-        mode != GNN_PART_SWITCHING) {
+        mode != GNN_PART_SWITCHING && mode != GNN_PART_SWITCHING_DEVICE) {
         err = "unknown partition mode"; return GNN_EINVAL;
     }
     if (mode == GNN_PART_USER && !user_part) { err = "user_part is null"; return GNN_EINVAL; }
@@ -415,9 +467,14 @@ gnn_status build_host_meta(int model, int64_t n, const int64_t* rowptr, const in
                     err = "user_part entry outside [0, k)";
                     return GNN_EINVAL;
                 }
-        } else if (mode == GNN_PART_SWITCHING) {
+        } else if (mode == GNN_PART_SWITCHING || mode == GNN_PART_SWITCHING_DEVICE) {
+            if (mode == GNN_PART_SWITCHING_DEVICE && k > switch_pref_max_k()) {
+                err = "GNN_PART_SWITCHING_DEVICE supports at most " + std::to_string(switch_pref_max_k()) +
+                      " partitions";
+                return GNN_EUNSUPPORTED;
+            }
             SwitchingInfo info;
-            assign_switching(n, rowptr, colidx, k, seed, M.part, info);
+            assign_switching(n, rowptr, colidx, k, seed, mode == GNN_PART_SWITCHING_DEVICE, M.part, info);
             M.part_iterations = info.iterations;
             M.part_objective = std::move(info.objective);
         } else {
@@ -558,6 +615,49 @@ gnn_status build_host_meta(int model, int64_t n, const int64_t* rowptr, const in
             });
         }
 
+        // ---- order in which an epoch walks the partitions -------------------------------------
+        // The next partition is the one that shares most blocks with the one just processed
+        // (its own block and the owners of its boundary rows), so that blocks already in the
+        // cache are reused before they are evicted; the 1-hop topology is fixed, so the order
+        // is too (appendix on I/O optimisations, overlap of cache management and computation).
+        // Starts at partition 0; equal overlaps go to the lower id.
+        {
+            const size_t words = ((size_t)k + 63) / 64;
+            std::vector<uint64_t> dep((size_t)k * words, 0);
+            parallel_for(k, 1, [&](int, int64_t p) {
+                uint64_t* d = dep.data() + (size_t)p * words;
+                d[(size_t)p / 64] |= 1ull << (p % 64);
+                const int32_t* b0 = M.bnd.data() + M.boff[(size_t)p];
+                const int32_t* b1 = M.bnd.data() + M.boff[(size_t)p + 1];
+                int32_t q = 0;
+                for (const int32_t* b = b0; b < b1;) {      // ascending rows: one hop per owner
+                    while (M.off[(size_t)q + 1] <= *b) ++q;
+                    d[(size_t)q / 64] |= 1ull << (q % 64);
+                    b = std::lower_bound(b, b1, (int32_t)M.off[(size_t)q + 1]);
+                }
+            });
+            M.sched.assign((size_t)k, 0);
+            std::vector<uint8_t> used((size_t)k, 0);
+            used[0] = 1;
+            const char* fixed = std::getenv("GNNMI_SCHEDULE");
+            const bool identity = fixed && std::strcmp(fixed, "identity") == 0;
+            for (int32_t t = 1; t < k; ++t) {
+                if (identity) { M.sched[(size_t)t] = t; continue; }
+                const uint64_t* dc = dep.data() + (size_t)M.sched[(size_t)t - 1] * words;
+                int32_t best = -1;
+                int64_t best_common = -1;
+                for (int32_t q = 0; q < k; ++q) {
+                    if (used[(size_t)q]) continue;
+                    const uint64_t* dq = dep.data() + (size_t)q * words;
+                    int64_t common = 0;
+                    for (size_t w = 0; w < words; ++w) common += __builtin_popcountll(dc[w] & dq[w]);
+                    if (common > best_common) { best_common = common; best = q; }
+                }
+                M.sched[(size_t)t] = best;
+                used[(size_t)best] = 1;
+            }
+        }
+
         // ---- phase C: transpose of every T_p ------------------------------------------------
         M.trp.assign((size_t)M.toff[(size_t)k] + 1, 0);
         M.tcol.resize((size_t)nnz);
@@ -617,6 +717,9 @@ gnn_status build_host_meta(int model, int64_t n, const int64_t* rowptr, const in
     } catch (const std::bad_alloc&) {
         err = "out of host memory while building partitions";
         return GNN_ENOMEM;
+    } catch (const HipFailure& f) {
+        err = f.what;
+        return GNN_EHIP;
     }
     return GNN_OK;
 }

@@ -51,7 +51,7 @@ struct BlockCache {
     std::vector<uint8_t> touched;   // write-back cache: block exists (on host or in a slot)
     char* host = nullptr;           // backing array of the current layer
     bool writeback = false;
-    int32_t cur_p = 0;              // partition whose accesses are being issued
+    int32_t cur_t = 0;              // step (position in the partition order) whose accesses are being issued
     int64_t tick = 0;
     int64_t loads = 0, hits = 0, writebacks = 0;
     char* ptr(int32_t s) const { return pool + (int64_t)s * slot_bytes; }
@@ -64,7 +64,8 @@ struct StreamEngine {
     char* pool = nullptr;           // hbm_budget bytes, carved into the two caches per layer
     int64_t pool_bytes = 0;
     BlockCache actc, gradc;
-    // next_dep[p * k + b] = first partition p' >= p that touches block b (k if none); row k is all k
+    // next_dep[t * k + b] = first step t' >= t whose partition touches block b (k if none);
+    // row k is all k.  Steps follow the order of HostMeta::sched.
     std::vector<int32_t> next_dep;
     int32_t k = 0;
     int64_t h2d_bytes = 0, d2h_bytes = 0;   // of the running epoch
@@ -132,37 +133,39 @@ gnn_status write_back(gnn_ctx* c, StreamEngine& E, BlockCache& bc, int32_t s)
     return GNN_OK;
 }
 
-// Position of "partition p touches block b" in the access order of a layer: partition by
-// partition, the own block first, then the other blocks in ascending order.
-inline int64_t access_pos(int32_t k, int32_t p, int32_t b)
+// Position of "step t touches block b" in the access order of a layer: step by step, the
+// step's own block first, then the other blocks in ascending order.
+inline int64_t access_pos(int32_t k, int32_t t, int32_t own, int32_t b)
 {
-    return (int64_t)p * (k + 1) + (b == p ? 0 : (int64_t)b + 1);
+    return (int64_t)t * (k + 1) + (b == own ? 0 : (int64_t)b + 1);
 }
 
-// Position of the first access to block b after position `now` of partition cur_p.
-int64_t next_use(const StreamEngine& E, int32_t cur_p, int64_t now, int32_t b)
+// Position of the first access to block b after position `now` of step cur_t.
+int64_t next_use(const StreamEngine& E, const std::vector<int32_t>& sched, int32_t cur_t, int64_t now,
+                 int32_t b)
 {
     const int32_t k = E.k;
-    if (E.next_dep[(size_t)cur_p * k + b] == cur_p) {
-        const int64_t here = access_pos(k, cur_p, b);
+    if (E.next_dep[(size_t)cur_t * k + b] == cur_t) {
+        const int64_t here = access_pos(k, cur_t, sched[(size_t)cur_t], b);
         if (here > now) return here;
     }
-    const int32_t p2 = E.next_dep[(size_t)(cur_p + 1) * k + b];
-    return p2 >= k ? INT64_MAX : access_pos(k, p2, b);
+    const int32_t t2 = E.next_dep[(size_t)(cur_t + 1) * k + b];
+    return t2 >= k ? INT64_MAX : access_pos(k, t2, sched[(size_t)t2], b);
 }
 
 // Chooses a slot for block `part`: a free one, else the unpinned one whose block is needed
 // again last (ties: the least recently used).
-int32_t pick_victim(const StreamEngine& E, const BlockCache& bc, int32_t part)
+int32_t pick_victim(const StreamEngine& E, const std::vector<int32_t>& sched, const BlockCache& bc,
+                    int32_t part)
 {
-    const int64_t now = access_pos(E.k, bc.cur_p, part);
+    const int64_t now = access_pos(E.k, bc.cur_t, sched[(size_t)bc.cur_t], part);
     int32_t best = -1;
     int64_t best_next = -1;
     for (int32_t s = 0; s < bc.nslots; ++s) {
         const Slot& sl = bc.slots[(size_t)s];
         if (sl.part < 0) return s;
         if (sl.pinned) continue;
-        const int64_t nu = next_use(E, bc.cur_p, now, sl.part);
+        const int64_t nu = next_use(E, sched, bc.cur_t, now, sl.part);
         if (best < 0 || nu > best_next ||
             (nu == best_next && sl.last_use < bc.slots[(size_t)best].last_use)) {
             best = s;
@@ -183,7 +186,7 @@ gnn_status acquire(gnn_ctx* c, StreamEngine& E, BlockCache& bc, int32_t part, hi
     if (s >= 0) {
         ++bc.hits;
     } else {
-        s = pick_victim(E, bc, part);
+        s = pick_victim(E, M.sched, bc, part);
         if (s < 0) {
             if (!wait) { *slot_out = -1; return GNN_OK; }
             return c->fail(GNN_ENOMEM, "streaming cache: every slot is pinned");
@@ -237,19 +240,19 @@ gnn_status mark_used(gnn_ctx* c, BlockCache& bc, int32_t s, hipStream_t compute,
 
 // Gather of partition p's boundary rows from the cached blocks of layer l-1, one source
 // partition at a time.  Leaves the own block pinned and returns its slot.
-gnn_status gather_from_cache(gnn_ctx* c, StreamEngine& E, int32_t layer, int32_t p, hipStream_t s,
+gnn_status gather_from_cache(gnn_ctx* c, StreamEngine& E, int32_t layer, int32_t t, hipStream_t s,
                              int32_t* own_slot)
 {
     const HostMeta& M = c->M;
-    const int32_t k = M.k;
+    const int32_t k = M.k, p = M.sched[(size_t)t];
     const int64_t row_bytes = (int64_t)c->dims[(size_t)layer - 1] * c->es();
-    E.actc.cur_p = p;
+    E.actc.cur_t = t;
     gnn_status st = acquire(c, E, E.actc, p, s, true, own_slot);
     if (st != GNN_OK) return st;
     E.actc.slots[(size_t)*own_slot].pinned = true;
     const int64_t* run = M.brun.data() + (size_t)p * ((size_t)k + 1);
     const int64_t b0 = M.boff[(size_t)p];
-    Timed t(c, s, GNN_K_GATHER);
+    Timed timed(c, s, GNN_K_GATHER);
     for (int32_t q = 0; q < k; ++q) {
         const int64_t len = run[q + 1] - run[q];
         if (len <= 0) continue;
@@ -262,17 +265,18 @@ gnn_status gather_from_cache(gnn_ctx* c, StreamEngine& E, int32_t layer, int32_t
     return GNN_OK;
 }
 
-// Issues loads for the blocks partition p will need, as long as unpinned slots are free or
-// older than everything p itself needs.
-gnn_status prefetch_for(gnn_ctx* c, StreamEngine& E, int32_t p, hipStream_t s)
+// Issues loads for the blocks the partition of step t will need, as long as a slot can be
+// taken for them.
+gnn_status prefetch_for(gnn_ctx* c, StreamEngine& E, int32_t t, hipStream_t s)
 {
     const HostMeta& M = c->M;
     const int32_t k = M.k;
-    if (p >= k) return GNN_OK;
+    if (t >= k) return GNN_OK;
+    const int32_t p = M.sched[(size_t)t];
     const int64_t* run = M.brun.data() + (size_t)p * ((size_t)k + 1);
     int32_t budget = E.actc.nslots - 1;      // never cycle the whole cache for a prefetch
     int32_t slot;
-    E.actc.cur_p = p;
+    E.actc.cur_t = t;
     gnn_status st = acquire(c, E, E.actc, p, s, false, &slot);
     if (st != GNN_OK) return st;
     --budget;
@@ -300,11 +304,12 @@ gnn_status stream_engine_create(gnn_ctx* c)
         const int32_t k = M.k;
         E->k = k;
         E->next_dep.assign(((size_t)k + 1) * (size_t)k, k);
-        for (int32_t p = k - 1; p >= 0; --p) {
+        for (int32_t t = k - 1; t >= 0; --t) {
+            const int32_t p = M.sched[(size_t)t];
             const int64_t* run = M.brun.data() + (size_t)p * ((size_t)k + 1);
             for (int32_t b = 0; b < k; ++b) {
                 const bool dep = b == p || run[b + 1] > run[b];
-                E->next_dep[(size_t)p * k + b] = dep ? p : E->next_dep[(size_t)(p + 1) * k + b];
+                E->next_dep[(size_t)t * k + b] = dep ? t : E->next_dep[(size_t)(t + 1) * k + b];
             }
         }
     }
@@ -438,12 +443,13 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
                        const_cast<char*>(c->layer_input(l)), false);
         if (st != GNN_OK) return st;
         const int64_t out_row = (int64_t)dout * c->act_es(l);
-        for (int32_t p = 0; p < k; ++p) {
+        for (int32_t t = 0; t < k; ++t) {
+            const int32_t p = M.sched[(size_t)t];
             const int64_t r0 = M.off[(size_t)p], np = M.off[(size_t)p + 1] - r0;
             int32_t own;
-            if ((st = gather_from_cache(c, E, l, p, s, &own)) != GNN_OK) return st;
-            if ((st = prefetch_for(c, E, p + 1, s)) != GNN_OK) return st;
-            const int ob = p & 1;
+            if ((st = gather_from_cache(c, E, l, t, s, &own)) != GNN_OK) return st;
+            if ((st = prefetch_for(c, E, t + 1, s)) != GNN_OK) return st;
+            const int ob = t & 1;
             if ((st = wait_out_free(ob)) != GNN_OK) return st;
             compute_fwd(c, l, p, E.actc.ptr(own), E.outbuf(ob), s);
             if ((st = mark_used(c, E.actc, own, s, false)) != GNN_OK) return st;
@@ -518,9 +524,10 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
             if (st != GNN_OK) return st;
         }
         // transfer buffers of partition p: its gradient block and (hidden layers) its activations
-        auto load_io = [&](int32_t p) -> gnn_status {
+        auto load_io = [&](int32_t t) -> gnn_status {
+            const int32_t p = M.sched[(size_t)t];
             const int64_t r0 = M.off[(size_t)p], np = M.off[(size_t)p + 1] - r0;
-            const int ib = p & 1;
+            const int ib = t & 1;
             gnn_status r = load_in(E.ginbuf(ib), (const char*)(c->gact[(size_t)l - 1] + r0 * dout),
                                    np * dout * 4, ib, true);
             if (r != GNN_OK) return r;
@@ -532,13 +539,14 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
             return GNN_OK;
         };
         if ((st = load_io(0)) != GNN_OK) return st;
-        for (int32_t p = 0; p < k; ++p) {
+        for (int32_t t = 0; t < k; ++t) {
+            const int32_t p = M.sched[(size_t)t];
             const int64_t np = M.off[(size_t)p + 1] - M.off[(size_t)p];
-            const int ib = p & 1;
+            const int ib = t & 1;
             int32_t own;
-            if ((st = gather_from_cache(c, E, l, p, s, &own)) != GNN_OK) return st;
-            if ((st = prefetch_for(c, E, p + 1, s)) != GNN_OK) return st;
-            if (p + 1 < k && (st = load_io(p + 1)) != GNN_OK) return st;
+            if ((st = gather_from_cache(c, E, l, t, s, &own)) != GNN_OK) return st;
+            if ((st = prefetch_for(c, E, t + 1, s)) != GNN_OK) return st;
+            if (t + 1 < k && (st = load_io(t + 1)) != GNN_OK) return st;
             GNN_HIP(hipStreamWaitEvent(s, E.in_ready[ib], 0));
             const char* dY = compute_bwd(c, l, p, E.actc.ptr(own), (const float*)E.ginbuf(ib),
                                          l < L ? E.ainbuf(ib) : nullptr, nullptr, s);
@@ -550,11 +558,11 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
                 const int64_t* run = M.brun.data() + (size_t)p * ((size_t)k + 1);
                 const int64_t b0 = M.boff[(size_t)p];
                 int32_t gown;
-                E.gradc.cur_p = p;
+                E.gradc.cur_t = t;
                 if ((st = acquire(c, E, E.gradc, p, s, true, &gown)) != GNN_OK) return st;
                 E.gradc.slots[(size_t)gown].pinned = true;
                 {
-                    Timed t(c, s, GNN_K_SCATTER);
+                    Timed timed(c, s, GNN_K_SCATTER);
                     launch_scatter_add(dGA, np, np, 0, nullptr, (float*)E.gradc.ptr(gown), din, s);
                     for (int32_t q = 0; q < k; ++q) {
                         const int64_t len = run[q + 1] - run[q];

@@ -1,7 +1,7 @@
 """Small shared test utilities (no method arithmetic of the GPU path, none of the oracle's)."""
 import numpy as np
 
-from synth import rmat_graph
+from synth import csr_from_edges, rmat_graph
 
 
 def small_graph(n, m_draw, seed, symmetric=True, self_loops=False):
@@ -94,3 +94,24 @@ def aligned_backward(og, fwd, got_act, weights, X, labels, mask, tol, say=None):
     out = og.backward(fwd, labels, mask, relu_on=relu_on)
     out["act"] = fwd.act
     return out
+
+
+def ring_of_blocks(k, per, seed):
+    """k groups of `per` vertices on a ring: every vertex aggregates from a few vertices of its
+    own group and of the next group on the ring; group ids are scrambled."""
+    rng = np.random.default_rng(seed)
+    label = rng.permutation(k)                       # position on the ring -> partition id
+    n = k * per
+    part = np.empty(n, dtype=np.int32)
+    src, dst = [], []
+    for pos in range(k):
+        ids = np.arange(pos * per, (pos + 1) * per)
+        part[ids] = label[pos]
+        nxt = np.arange(((pos + 1) % k) * per, ((pos + 1) % k + 1) * per)
+        for v in ids:
+            for u in list(rng.choice(ids, 3, replace=False)) + list(rng.choice(nxt, 2, replace=False)):
+                src.append(int(u)); dst.append(int(v))
+                src.append(int(v)); dst.append(int(u))
+    pairs = np.unique(np.array(dst, dtype=np.int64) * n + np.array(src, dtype=np.int64))
+    rowptr, colidx = csr_from_edges(n, pairs % n, pairs // n)
+    return rowptr, colidx, part, label

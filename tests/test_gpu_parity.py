@@ -8,7 +8,7 @@ import sys
 import numpy as np
 import pytest
 
-from helpers import aligned_backward, empty_graph, rel_err, small_graph
+from helpers import aligned_backward, empty_graph, rel_err, ring_of_blocks, small_graph
 from oracle import fullgraph as og
 from oracle import partition as op
 from synth import features, glorot_weights, labels_and_mask, make_config
@@ -317,6 +317,39 @@ def test_streaming_schedule_is_bit_identical_to_resident(case):
     assert e.value.status == 5
 
 
+def test_streaming_partition_order_reuses_cached_blocks(monkeypatch):
+    say("case streaming with the reuse order against the id order")
+    from paper_2605_11517_amd import Session
+    k, per = 12, 40
+    rowptr, colidx, part, _ = ring_of_blocks(k, per, seed=4)
+    n = k * per
+    cfg = dict(model="sage", dims=(16, 16, 8, 4), seed=5, train_frac=0.5)
+    X, y, m, w = make_inputs(cfg, n)
+    ref = og.epoch("sage", rowptr, colidx, cfg["dims"], X, w, y, m)
+    loads = {}
+    for order in ("reuse", "identity"):
+        if order == "identity":
+            monkeypatch.setenv("GNNMI_SCHEDULE", "identity")
+        res = Session("sage", cfg["dims"], rowptr, colidx, k, "user", 0, X, w, y, m, user_part=part)
+        loss_res = res.epoch()
+        r_res = res.results()
+        compare(r_res, ref, "sage", tag="ring-" + order)
+        slot = (per * 16 * 4 + 255) // 256 * 256
+        s = Session("sage", cfg["dims"], rowptr, colidx, k, "user", 0, X, w, y, m, user_part=part,
+                    hbm_budget_bytes=4 * slot)
+        assert list(s.ctx.get_schedule()) == list(res.ctx.get_schedule())
+        if order == "identity":
+            assert list(s.ctx.get_schedule()) == list(range(k))
+        assert s.epoch() == loss_res
+        r = s.results()
+        for key in ("act", "gact", "gW", "gWs", "gb"):
+            for a, b in zip(r[key], r_res[key]):
+                assert np.array_equal(a, b), (order, key)
+        loads[order] = s.ctx.get_stream_stats()["act_loads"]
+    say("  activation block loads: reuse order %d, id order %d" % (loads["reuse"], loads["identity"]))
+    assert loads["reuse"] < loads["identity"]
+
+
 def test_empty_graph_and_empty_partitions():
     say("case empty graph / empty partitions")
     n, dims = 40, (8, 8, 4)
@@ -351,3 +384,18 @@ def test_result_does_not_depend_on_k():
         for key in ("act", "gW", "gb", "gact"):
             for a, b in zip(r[key], base[key]):
                 assert rel_err(a, b) <= TOL, (key, k)
+
+
+@pytest.mark.parametrize("name,k", [("tiny", 4), ("mini_sage", 37), ("mini_gcn_directed", 7), ("tiny", 1)])
+def test_device_preference_counting_gives_the_host_partitioners_assignment(name, k):
+    say("case switching partitioner on the device %s k=%d" % (name, k))
+    from paper_2605_11517_amd import Context
+    cfg, rowptr, colidx = make_config(name)
+    host = Context(cfg["model"], cfg["dims"])
+    host.build_partitions(rowptr, colidx, k, "switching", 9)
+    dev = Context(cfg["model"], cfg["dims"])
+    dev.build_partitions(rowptr, colidx, k, "switching_device", 9)
+    assert np.array_equal(host.get_partition()[0], dev.get_partition()[0])
+    ih, oh = host.get_partitioner_history()
+    idv, od = dev.get_partitioner_history()
+    assert ih == idv and oh == od             # the objective is an exact integer on both sides

@@ -7,7 +7,7 @@ import re
 import numpy as np
 import pytest
 
-from helpers import small_graph
+from helpers import ring_of_blocks, small_graph
 from oracle import partition as op
 from paper_2605_11517_amd import Context, GnnError, load_library
 from synth import make_config
@@ -166,3 +166,22 @@ def test_switching_assignment_does_not_depend_on_the_thread_count(monkeypatch):
     assert np.array_equal(got[0], got[1]) and np.array_equal(got[0], got[2])
     sizes = np.bincount(got[0], minlength=6)
     assert sizes.max() <= (11 * cfg["n"]) // (10 * 6)
+
+
+def test_partition_order_follows_shared_blocks():
+    k, per = 9, 12
+    rowptr, colidx, part, label = ring_of_blocks(k, per, seed=4)
+    ctx = Context("gcn", (4, 4, 2))
+    ctx.build_partitions(rowptr, colidx, k, "user", 0, user_part=part)
+    sched = ctx.get_schedule()
+    assert sorted(sched) == list(range(k)) and sched[0] == 0
+    assert list(sched) == op.reuse_order(rowptr, colidx, part, k)
+    # consecutive partitions of the order are neighbours on the ring, which the id order is not
+    pos = {int(label[i]): i for i in range(k)}
+    hops = [min((pos[int(a)] - pos[int(b)]) % k, (pos[int(b)] - pos[int(a)]) % k)
+            for a, b in zip(sched[:-1], sched[1:])]
+    assert sum(h == 1 for h in hops) >= k - 2
+    # all-to-all dependencies leave the id order in place
+    cfg, rp, ci = make_config("tiny")
+    ctx.build_partitions(rp, ci, 4, "random", 1)
+    assert list(ctx.get_schedule()) == [0, 1, 2, 3]
