@@ -262,14 +262,18 @@ double oracle_loss(int64_t n, int64_t C, const double *logits, const int32_t *la
  * W[l]     [d_l, d_{l+1}]   (GCN weight, or SAGE neighbour weight W_n)      l = 0..L-1
  * Ws[l]    [d_l, d_{l+1}]   SAGE self weight (ignored for GCN; may be NULL)
  * b[l]     [d_{l+1}]        bias (may be NULL = no bias)
+ * drop[l]  [n, d_{l+1}]     optional (NULL array or NULL entries): dropout multipliers of hidden
+ *                           layer l+1, each 0 or 1/(1-p), applied after the activation (training
+ *                           with the dropout rates of the datasets table); the random draws are
+ *                           an input, made by the caller
  * act[l]   [n, d_{l+1}]     out: A^{l+1}
  * zagg[l]  [n, d_l]         out: aggregated input Z of layer l+1
  * Returns 0, or -1 when memory runs out.
  */
 int oracle_forward(int model, int64_t n, const int64_t *rowptr, const int32_t *colidx, int L,
                    const int32_t *dims, const double *X, const double *const *W,
-                   const double *const *Ws, const double *const *b, double *const *act,
-                   double *const *zagg)
+                   const double *const *Ws, const double *const *b, const double *const *drop,
+                   double *const *act, double *const *zagg)
 {
     agg_op op;
     if (agg_build(model, n, rowptr, colidx, &op)) {
@@ -288,6 +292,7 @@ int oracle_forward(int model, int64_t n, const int64_t *rowptr, const int32_t *c
             for (int64_t c = 0; c < dout; ++c) {
                 double y = Y[v * dout + c] + (b && b[l] ? b[l][c] : 0.0);
                 if (l < L - 1 && !(y > 0.0)) y = 0.0;
+                if (l < L - 1 && drop && drop[l]) y *= drop[l][v * dout + c];
                 Y[v * dout + c] = y;
             }
     }
@@ -304,6 +309,7 @@ int oracle_forward(int model, int64_t n, const int64_t *rowptr, const int32_t *c
  *                      test that compares against an fp32 implementation passes the other
  *                      side's decision for the few elements whose pre-activation lies within
  *                      rounding distance of zero, where either choice is a correct result.
+ * drop                 the multipliers the forward pass used (or NULL)
  * gW, gWs, gb          out: gradients, same shapes as W, Ws, b (NULL entries skipped)
  * gact[l]  [n, d_{l+1}]     out: dLoss/dA^{l+1}  (NULL array or NULL entries skipped)
  * gX       [n, d_0]         out (optional): dLoss/dA^0.  The training pass does not need it
@@ -316,7 +322,7 @@ int oracle_backward(int model, int64_t n, const int64_t *rowptr, const int32_t *
                     const int32_t *dims, const double *X, const double *const *W,
                     const double *const *Ws, const double *const *act, const double *const *zagg,
                     const int32_t *labels, const uint8_t *mask, const uint8_t *const *relu_on,
-                    double *loss, double *const *gW, double *const *gWs, double *const *gb,
+                    const double *const *drop, double *loss, double *const *gW, double *const *gWs, double *const *gb,
                     double *const *gact, double *gX)
 {
     agg_op op;
@@ -345,6 +351,7 @@ int oracle_backward(int model, int64_t n, const int64_t *rowptr, const int32_t *
             int pass = 1;
             if (l < L - 1) pass = on ? (on[i] != 0) : (act[l][i] > 0.0);
             dY[i] = pass ? G[i] : 0.0;
+            if (l < L - 1 && drop && drop[l]) dY[i] *= drop[l][i];
         }
         if (gb && gb[l])
             for (int64_t c = 0; c < dout; ++c) {
