@@ -243,6 +243,45 @@ gnn_status gnn_layer_bwd(gnn_ctx *ctx, int32_t layer, int32_t p, void *stream);
  * Synchronises `stream` before writing *loss_out (host). */
 gnn_status gnn_epoch(gnn_ctx *ctx, void *stream, float *loss_out);
 
+/* ---- training around the epoch (datasets table: learning rate, dropout, epochs) ---------- */
+
+/* Dropout with rate p in [0, 1) after the activation of every hidden layer in the epochs
+ * that follow; p = 0 (the default) switches it off.  The paper fixes only the rate.  The
+ * draws are counter-based, so nothing is stored for the backward pass (the dropped elements
+ * are the zeros of the stored activation) and the result does not depend on the
+ * partitioning: element (v, j) of hidden layer l (1-based; v an original vertex id, d the
+ * layer's width) draws splitmix64(key + v d + j) >> 32 with
+ * key = splitmix64(seed ^ splitmix64(64 epoch_index + l)) and is zeroed when the draw is
+ * below floor(p 2^32), otherwise multiplied by 1 / (1 - p) in fp32.  GNN_EINVAL outside
+ * [0, 1). */
+gnn_status gnn_set_dropout(gnn_ctx *ctx, float p, uint64_t seed, int64_t epoch_index);
+
+typedef enum { GNN_OPT_SGD = 0, GNN_OPT_ADAM = 1 } gnn_opt_kind;
+typedef struct {
+    int32_t kind;        /* gnn_opt_kind */
+    float lr;
+    float beta1, beta2;  /* Adam */
+    float eps;           /* Adam */
+    float weight_decay;  /* added to the gradient as weight_decay * w */
+} gnn_optimizer;
+
+/* Adam moment buffers (device, fp32, zeroed by the caller before the first step), laid out
+ * like `weights` in gnn_bind: 3 L entries, null where the tensor does not exist.  Caller
+ * owned.  Not needed for GNN_OPT_SGD. */
+gnn_status gnn_bind_optimizer(gnn_ctx *ctx, void *const *m, void *const *v);
+
+/* The bound weight buffers are updated in place: weights <- one optimizer step from grad_w
+ * (as left by the last epoch); `step` is the
+ * 1-based step number (Adam's bias correction).  fp32 weights only: GNN_EUNSUPPORTED for
+ * GNN_BF16.  GNN_ESTATE when nothing is bound (or, for Adam, no moments). */
+gnn_status gnn_optimizer_step(gnn_ctx *ctx, const gnn_optimizer *opt, int64_t step, void *stream);
+
+/* `epochs` times: gnn_set_dropout(p, seed, first_epoch + e), gnn_epoch, gnn_optimizer_step
+ * with step first_epoch + e + 1; losses[e] (host) receives each epoch's loss.  Leaves
+ * dropout configured for the last epoch. */
+gnn_status gnn_train(gnn_ctx *ctx, const gnn_optimizer *opt, int32_t epochs, int64_t first_epoch,
+                     float dropout_p, uint64_t dropout_seed, void *stream, float *losses);
+
 /* ---- measurement ------------------------------------------------------------------------ */
 
 /* When enabled, every kernel class of gnn_epoch is bracketed by HIP events on `stream`

@@ -45,6 +45,15 @@ class _Stats(C.Structure):
                 ("max_own", C.c_int64), ("max_boundary", C.c_int64), ("max_nnz", C.c_int64)]
 
 
+class Optimizer(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float),
+                ("eps", C.c_float), ("weight_decay", C.c_float)]
+
+
+def make_optimizer(kind="adam", lr=0.01, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0):
+    return Optimizer({"sgd": 0, "adam": 1}[kind], lr, beta1, beta2, eps, weight_decay)
+
+
 class StreamStats(C.Structure):
     _fields_ = [(f, C.c_int64) for f in ("act_loads", "act_hits", "grad_loads", "grad_hits",
                                          "grad_writebacks", "h2d_bytes", "d2h_bytes")]
@@ -80,6 +89,10 @@ def load_library():
         "gnn_read_loss": [vp, vp, P(C.c_float)],
         "gnn_layer_bwd": [vp, i32, i32, vp],
         "gnn_epoch": [vp, vp, P(C.c_float)],
+        "gnn_set_dropout": [vp, C.c_float, u64, i64],
+        "gnn_bind_optimizer": [vp, P(vp), P(vp)],
+        "gnn_optimizer_step": [vp, P(Optimizer), i64, vp],
+        "gnn_train": [vp, P(Optimizer), i32, i64, C.c_float, u64, vp, P(C.c_float)],
         "gnn_set_profiling": [vp, i32],
         "gnn_get_profile": [vp, P(C.c_double), P(i64)],
         "gnn_get_stream_stats": [vp, P(StreamStats)],
@@ -227,6 +240,26 @@ class Context:
         self._check(self.lib.gnn_epoch(self.h, stream, C.byref(v)))
         return float(v.value)
 
+    def set_dropout(self, p, seed, epoch_index):
+        self._check(self.lib.gnn_set_dropout(self.h, float(p), int(seed), int(epoch_index)))
+
+    def bind_optimizer(self, m, v):
+        def arr(ptrs):
+            a = (C.c_void_p * max(1, len(ptrs)))()
+            for i, p in enumerate(ptrs):
+                a[i] = p
+            return a
+        self._check(self.lib.gnn_bind_optimizer(self.h, arr(m), arr(v)))
+
+    def optimizer_step(self, opt, step, stream):
+        self._check(self.lib.gnn_optimizer_step(self.h, C.byref(opt), int(step), stream))
+
+    def train(self, opt, epochs, first_epoch, dropout_p, dropout_seed, stream):
+        losses = (C.c_float * max(1, epochs))()
+        self._check(self.lib.gnn_train(self.h, C.byref(opt), int(epochs), int(first_epoch),
+                                       float(dropout_p), int(dropout_seed), stream, losses))
+        return [float(losses[i]) for i in range(epochs)]
+
     def set_profiling(self, enabled):
         self._check(self.lib.gnn_set_profiling(self.h, 1 if enabled else 0))
 
@@ -350,4 +383,29 @@ class Session:
             out["gW"].append(gW.cpu().numpy())
             out["gWs"].append(gWs.cpu().numpy() if gWs is not None else None)
             out["gb"].append(gb.cpu().numpy() if gb is not None else None)
+        return out
+
+    # -- training around the epoch -------------------------------------------------------------
+    def train(self, epochs, optimizer="adam", lr=0.01, beta1=0.9, beta2=0.999, eps=1e-8,
+              weight_decay=0.0, dropout=0.0, seed=0, first_epoch=0):
+        """``epochs`` times epoch + optimizer step on the bound weights; returns the losses."""
+        t = self.torch
+        if optimizer == "adam" and not hasattr(self, "opt_m"):
+            self.opt_m = [None if w is None else t.zeros(w.shape, dtype=t.float32, device=self.dev)
+                          for w in self.w]
+            self.opt_v = [None if w is None else t.zeros(w.shape, dtype=t.float32, device=self.dev)
+                          for w in self.w]
+            ptr = lambda x: x.data_ptr() if x is not None else None
+            self.ctx.bind_optimizer([ptr(x) for x in self.opt_m], [ptr(x) for x in self.opt_v])
+        opt = make_optimizer(optimizer, lr, beta1, beta2, eps, weight_decay)
+        return self.ctx.train(opt, epochs, first_epoch, dropout, seed, self.stream)
+
+    def weights(self):
+        """The bound weights as a list of dicts of numpy arrays (the layout of ``weights``)."""
+        out = []
+        for l in range(self.L):
+            W, Ws, b = self.w[3 * l:3 * l + 3]
+            out.append({"W": W.float().cpu().numpy(),
+                        "Ws": Ws.float().cpu().numpy() if Ws is not None else None,
+                        "b": b.float().cpu().numpy() if b is not None else None})
         return out

@@ -2,6 +2,7 @@
 // per-(layer, partition) schedule of the paper's overall procedure (forward: gather, FW;
 // backward: regather, BW, scatter-accumulate).
 #include <algorithm>
+#include <cmath>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -210,6 +211,14 @@ void zero_weight_grads(gnn_ctx* c, hipStream_t s)
     }
 }
 
+static inline uint64_t splitmix64(uint64_t x)
+{
+    uint64_t z = x + 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
 void compute_fwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, char* out_own, hipStream_t s)
 {
     const HostMeta& M = c->M;
@@ -241,6 +250,12 @@ void compute_fwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, char*
         launch_gemm_bf16_nn(seg, sage ? 2 : 1, out_own, layer < c->L ? 1 : 0 /* logits stay fp32 */, dout,
                             np, dout, ep, s);
     }
+    if (c->dropout_p > 0.f && layer < c->L) {
+        const uint64_t key = splitmix64(c->dropout_seed ^ splitmix64((uint64_t)(64 * c->dropout_epoch + layer)));
+        const uint32_t threshold = (uint32_t)std::floor((double)c->dropout_p * 4294967296.0);
+        launch_dropout(out_own, c->bf16() ? 1 : 0, c->D.order + M.off[(size_t)p], np, dout, key, threshold,
+                       1.f / (1.f - c->dropout_p), s);
+    }
 }
 
 const char* compute_bwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, const float* g_own,
@@ -266,16 +281,18 @@ const char* compute_bwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own
 
     // activation backward: dY = grad A ⊙ [A > 0] on hidden layers, grad A itself on the last
     const char* dY = (const char*)g_own;
+    const float drop_scale = c->dropout_p > 0.f ? 1.f / (1.f - c->dropout_p) : 1.f;
     {
         Timed t(c, s, GNN_K_ACT_BWD);
         if (b16) {
-            launch_act_bwd_bf16(g_own, layer < L ? act_own : nullptr, dYbuf, np, dout, gb, colpart, s);
+            launch_act_bwd_bf16(g_own, layer < L ? act_own : nullptr, dYbuf, np, dout, gb, colpart,
+                                drop_scale, s);
             dY = dYbuf;
         } else if (layer < L) {
-            launch_act_bwd(g_own, (const float*)act_own, (float*)dYbuf, np, dout, gb, colpart, s);
+            launch_act_bwd(g_own, (const float*)act_own, (float*)dYbuf, np, dout, gb, colpart, drop_scale, s);
             dY = dYbuf;
         } else {
-            launch_act_bwd(g_own, nullptr, nullptr, np, dout, gb, colpart, s);
+            launch_act_bwd(g_own, nullptr, nullptr, np, dout, gb, colpart, 1.f, s);
         }
     }
     // recompute the aggregate from the regathered rows
@@ -680,6 +697,80 @@ gnn_status gnn_epoch(gnn_ctx* c, void* stream, float* loss_out)
         }
     if ((st = gnn_read_loss(c, stream, loss_out)) != GNN_OK) return st;
     if (c->prof) collect_profile(c);
+    return GNN_OK;
+}
+
+gnn_status gnn_set_dropout(gnn_ctx* c, float p, uint64_t seed, int64_t epoch_index)
+{
+    if (!c) return GNN_EINVAL;
+    if (!(p >= 0.f && p < 1.f)) return c->fail(GNN_EINVAL, "dropout rate must lie in [0, 1)");
+    c->dropout_p = p;
+    c->dropout_seed = seed;
+    c->dropout_epoch = epoch_index;
+    return GNN_OK;
+}
+
+gnn_status gnn_bind_optimizer(gnn_ctx* c, void* const* m, void* const* v)
+{
+    if (!c || !m || !v) return GNN_EINVAL;
+    const int32_t L = c->L;
+    c->opt_m.assign((size_t)3 * L, nullptr);
+    c->opt_v.assign((size_t)3 * L, nullptr);
+    for (int32_t l = 0; l < L; ++l)
+        for (int j = 0; j < 3; ++j) {
+            const bool needed = j == 0 || (j == 1 && c->model == GNN_SAGE_MEAN) || (j == 2 && c->has_bias);
+            if (needed && (!m[3 * l + j] || !v[3 * l + j])) {
+                c->opt_m.clear();
+                c->opt_v.clear();
+                return c->fail(GNN_EINVAL, "gnn_bind_optimizer: a moment buffer of an existing tensor is null");
+            }
+            c->opt_m[(size_t)(3 * l + j)] = (float*)m[3 * l + j];
+            c->opt_v[(size_t)(3 * l + j)] = (float*)v[3 * l + j];
+        }
+    return GNN_OK;
+}
+
+gnn_status gnn_optimizer_step(gnn_ctx* c, const gnn_optimizer* opt, int64_t step, void* stream)
+{
+    if (!c || !opt) return GNN_EINVAL;
+    if (!c->bound) return c->fail(GNN_ESTATE, "gnn_optimizer_step before gnn_bind");
+    if (c->bf16()) return c->fail(GNN_EUNSUPPORTED, "the optimizer step takes fp32 weights");
+    if (opt->kind != GNN_OPT_SGD && opt->kind != GNN_OPT_ADAM) return c->fail(GNN_EINVAL, "unknown optimizer");
+    if (step < 1) return c->fail(GNN_EINVAL, "step numbers start at 1");
+    if (opt->kind == GNN_OPT_ADAM && c->opt_m.empty())
+        return c->fail(GNN_ESTATE, "Adam needs gnn_bind_optimizer");
+    hipStream_t s = (hipStream_t)stream;
+    const float corr1 = (float)(1.0 / (1.0 - std::pow((double)opt->beta1, (double)step)));
+    const float corr2 = (float)(1.0 / (1.0 - std::pow((double)opt->beta2, (double)step)));
+    Timed t(c, s, GNN_K_OTHER);
+    for (int32_t l = 0; l < c->L; ++l)
+        for (int j = 0; j < 3; ++j) {
+            float* w = (float*)const_cast<char*>(c->w[(size_t)(3 * l + j)]);
+            float* g = c->gw[(size_t)(3 * l + j)];
+            if (!w || !g) continue;
+            if (j == 1 && c->model != GNN_SAGE_MEAN) continue;
+            if (j == 2 && !c->has_bias) continue;
+            const int64_t cnt = j == 2 ? (int64_t)c->dims[(size_t)l + 1]
+                                       : (int64_t)c->dims[(size_t)l] * c->dims[(size_t)l + 1];
+            if (opt->kind == GNN_OPT_ADAM)
+                launch_adam(w, g, c->opt_m[(size_t)(3 * l + j)], c->opt_v[(size_t)(3 * l + j)], cnt, opt->lr,
+                            opt->beta1, opt->beta2, opt->eps, opt->weight_decay, corr1, corr2, s);
+            else
+                launch_sgd(w, g, cnt, opt->lr, opt->weight_decay, s);
+        }
+    return check_launch(c, "gnn_optimizer_step");
+}
+
+gnn_status gnn_train(gnn_ctx* c, const gnn_optimizer* opt, int32_t epochs, int64_t first_epoch,
+                     float dropout_p, uint64_t dropout_seed, void* stream, float* losses)
+{
+    if (!c || !opt || !losses || epochs < 0 || first_epoch < 0) return GNN_EINVAL;
+    gnn_status st;
+    for (int32_t e = 0; e < epochs; ++e) {
+        if ((st = gnn_set_dropout(c, dropout_p, dropout_seed, first_epoch + e)) != GNN_OK) return st;
+        if ((st = gnn_epoch(c, stream, &losses[e])) != GNN_OK) return st;
+        if ((st = gnn_optimizer_step(c, opt, first_epoch + e + 1, stream)) != GNN_OK) return st;
+    }
     return GNN_OK;
 }
 

@@ -60,6 +60,10 @@ struct gnn_ctx {
     std::vector<float*> gact;
     std::vector<const char*> w;          // W, W_s: dtype; b: fp32
     std::vector<float*> gw;
+    std::vector<float*> opt_m, opt_v;    // Adam moments, bound by gnn_bind_optimizer
+    float dropout_p = 0.f;               // training: dropout rate after hidden activations
+    uint64_t dropout_seed = 0;
+    int64_t dropout_epoch = 0;
     const int32_t* labels = nullptr;
     const uint8_t* mask = nullptr;
     char* staging = nullptr;

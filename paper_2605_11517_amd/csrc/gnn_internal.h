@@ -174,12 +174,14 @@ void launch_to_bf16(const float* src, void* dst, int64_t n, hipStream_t s);
 // bfloat16 variant of the activation backward: g fp32, act bfloat16 (or null), dy bfloat16
 // (always written, because the contractions that follow take bfloat16 operands).
 void launch_act_bwd_bf16(const float* g, const void* act, void* dy, int64_t rows, int32_t d,
-                         float* gb, float* partial, hipStream_t s);
+                         float* gb, float* partial, float scale, hipStream_t s);
 
-// dy = g * (act > 0) (or dy = g when act == null); colsum partials then gb += colsum.
+// dy = scale * g * (act > 0) (or dy = g when act == null); colsum partials then gb += colsum.
+// scale = 1 / (1 - p) when dropout followed the activation (the dropped elements are the
+// zeros of act), else 1.
 // `partial` holds ceil(rows / 64) * d floats.
 void launch_act_bwd(const float* g, const float* act, float* dy, int64_t rows, int32_t d,
-                    float* gb, float* partial, hipStream_t s);
+                    float* gb, float* partial, float scale, hipStream_t s);
 int64_t act_bwd_partial_floats(int64_t rows, int32_t d);
 
 // softmax cross-entropy over masked rows; grad[n, c]; *loss_dev = mean loss.  count_dev
@@ -197,6 +199,14 @@ void launch_loss_finish(const float* partial, int64_t nparts, const unsigned lon
                         float* loss_dev, hipStream_t s);
 
 void launch_fill_zero(void* p, int64_t bytes, hipStream_t s);
+
+// Training pieces: dropout on a block of activation rows (orig_of_row[r] = original vertex id
+// of row r), and the optimizer steps on one fp32 parameter tensor.
+void launch_dropout(void* a, int is_bf16, const int32_t* orig_of_row, int64_t rows, int32_t d,
+                    uint64_t key, uint32_t threshold, float scale, hipStream_t s);
+void launch_adam(float* w, const float* g, float* m, float* v, int64_t n, float lr, float beta1,
+                 float beta2, float eps, float weight_decay, float corr1, float corr2, hipStream_t s);
+void launch_sgd(float* w, const float* g, int64_t n, float lr, float weight_decay, hipStream_t s);
 
 // Step 1 of one iteration of the switching-aware partitioner for every vertex: first and second
 // preference (second = -1 if there is none) from the assignment `part` and the partition sizes;

@@ -106,13 +106,14 @@ __global__ __launch_bounds__(kBlock) void k_loss_finish(const float* __restrict_
     if (threadIdx.x == 0) *loss = sm[0] * inv_count;
 }
 
-// dy = g * [act > 0] (act == null: dy aliases g, nothing is written) and per-block column
+// dy = scale * g * [act > 0] (act == null: dy aliases g, nothing is written) and per-block column
 // sums of dy into partial[block][d].  A block covers 64 rows; thread t walks columns
 // t, t + 256, ... so that a row segment is read coalesced.
 __global__ __launch_bounds__(kBlock) void k_act_bwd(const float* __restrict__ g,
                                                     const float* __restrict__ act,
                                                     float* __restrict__ dy, int64_t rows,
-                                                    int32_t d, float* __restrict__ partial)
+                                                    int32_t d, float* __restrict__ partial,
+                                                    float scale)
 {
     const int64_t r0 = (int64_t)blockIdx.x * kRowsPerBlockAct;
     const int64_t r1 = r0 + kRowsPerBlockAct < rows ? r0 + kRowsPerBlockAct : rows;
@@ -121,7 +122,7 @@ __global__ __launch_bounds__(kBlock) void k_act_bwd(const float* __restrict__ g,
         for (int64_t r = r0; r < r1; ++r) {
             float v = g[r * d + c];
             if (act) {
-                v = act[r * d + c] > 0.f ? v : 0.f;
+                v = act[r * d + c] > 0.f ? v * scale : 0.f;
                 dy[r * d + c] = v;
             }
             s += v;
@@ -136,7 +137,8 @@ __global__ __launch_bounds__(kBlock) void k_act_bwd(const float* __restrict__ g,
 __global__ __launch_bounds__(kBlock) void k_act_bwd_vec(const float* __restrict__ g,
                                                         const float* __restrict__ act,
                                                         float* __restrict__ dy, int64_t rows,
-                                                        int32_t d, float* __restrict__ partial)
+                                                        int32_t d, float* __restrict__ partial,
+                                                        float scale)
 {
     __shared__ float4 sm[kBlock];
     const int cw = d / 4;
@@ -165,10 +167,10 @@ __global__ __launch_bounds__(kBlock) void k_act_bwd_vec(const float* __restrict_
                 for (int u = 0; u < U; ++u) {
                     const int64_t rr = r + (int64_t)u * rpp;
                     float4 v = gv[u];
-                    v.x = av[u].x > 0.f ? v.x : 0.f;
-                    v.y = av[u].y > 0.f ? v.y : 0.f;
-                    v.z = av[u].z > 0.f ? v.z : 0.f;
-                    v.w = av[u].w > 0.f ? v.w : 0.f;
+                    v.x = av[u].x > 0.f ? v.x * scale : 0.f;
+                    v.y = av[u].y > 0.f ? v.y * scale : 0.f;
+                    v.z = av[u].z > 0.f ? v.z * scale : 0.f;
+                    v.w = av[u].w > 0.f ? v.w * scale : 0.f;
                     if (act && rr < r1) reinterpret_cast<float4*>(dy + rr * d)[cidx] = v;
                     s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
                 }
@@ -193,7 +195,8 @@ __global__ __launch_bounds__(kBlock) void k_act_bwd_vec(const float* __restrict_
 __global__ __launch_bounds__(kBlock) void k_act_bwd_bf16(const float* __restrict__ g,
                                                          const uint16_t* __restrict__ act,
                                                          uint16_t* __restrict__ dy, int64_t rows,
-                                                         int32_t d, float* __restrict__ partial)
+                                                         int32_t d, float* __restrict__ partial,
+                                                         float scale)
 {
     const int64_t r0 = (int64_t)blockIdx.x * kRowsPerBlockAct;
     const int64_t r1 = r0 + kRowsPerBlockAct < rows ? r0 + kRowsPerBlockAct : rows;
@@ -213,7 +216,7 @@ __global__ __launch_bounds__(kBlock) void k_act_bwd_bf16(const float* __restrict
             for (int u = 0; u < U; ++u) {
                 // positive bfloat16: sign bit clear and not zero
                 const bool pos = (av[u] & 0x8000u) == 0 && (av[u] & 0x7FFFu) != 0;
-                const float v = pos ? gv[u] : 0.f;
+                const float v = pos ? gv[u] * scale : 0.f;
                 if (r + u < r1) {
                     const uint32_t b = __float_as_uint(v);
                     dy[(r + u) * d + c] = (uint16_t)((b + 0x7FFFu + ((b >> 16) & 1u)) >> 16);
@@ -251,6 +254,66 @@ __global__ __launch_bounds__(kBlock) void k_colsum_finish(const float* __restric
         for (int q = 1; q < 8; ++q) s += sm[q][tx];
         gb[c] += s;
     }
+}
+
+// Dropout after a hidden layer's activation (training): element (v, j), v an original vertex
+// id, draws the upper 32 bits of splitmix64(key + v d + j) and is zeroed when the draw is below
+// `threshold`, otherwise multiplied by `scale` = 1 / (1 - p).  Counter-based: the same element
+// gets the same draw whatever partition its row is processed in.
+__device__ inline unsigned long long splitmix64_dev(unsigned long long x)
+{
+    unsigned long long z = x + 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+template <typename T>
+__global__ __launch_bounds__(kBlock) void k_dropout(T* __restrict__ a, const int32_t* __restrict__ orig,
+                                                    int64_t rows, int32_t d, unsigned long long key,
+                                                    unsigned int threshold, float scale)
+{
+    const int64_t total = rows * d;
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < total;
+         i += (int64_t)gridDim.x * kBlock) {
+        const int64_t r = i / d;
+        const int32_t j = (int32_t)(i - r * d);
+        const unsigned long long idx = (unsigned long long)orig[r] * (unsigned long long)d + (unsigned long long)j;
+        const unsigned int draw = (unsigned int)(splitmix64_dev(key + idx) >> 32);
+        if constexpr (sizeof(T) == 4) {
+            a[i] = draw < threshold ? 0.f : a[i] * scale;
+        } else {
+            const float v = draw < threshold ? 0.f : __uint_as_float((uint32_t)a[i] << 16) * scale;
+            const uint32_t b = __float_as_uint(v);
+            a[i] = (T)((b + 0x7FFFu + ((b >> 16) & 1u)) >> 16);
+        }
+    }
+}
+
+// One optimizer step over a parameter tensor of n floats.
+__global__ __launch_bounds__(kBlock) void k_adam(float* __restrict__ w, const float* __restrict__ g,
+                                                 float* __restrict__ m, float* __restrict__ v, int64_t n,
+                                                 float lr, float beta1, float beta2, float eps,
+                                                 float weight_decay, float corr1, float corr2)
+{
+    const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i >= n) return;
+    const float wi = w[i];
+    const float gi = g[i] + weight_decay * wi;
+    const float mi = beta1 * m[i] + (1.f - beta1) * gi;
+    const float vi = beta2 * v[i] + (1.f - beta2) * gi * gi;
+    m[i] = mi;
+    v[i] = vi;
+    w[i] = wi - lr * (mi * corr1) / (sqrtf(vi * corr2) + eps);
+}
+
+__global__ __launch_bounds__(kBlock) void k_sgd(float* __restrict__ w, const float* __restrict__ g,
+                                                int64_t n, float lr, float weight_decay)
+{
+    const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i >= n) return;
+    const float wi = w[i];
+    w[i] = wi - lr * (g[i] + weight_decay * wi);
 }
 
 }  // namespace
@@ -298,8 +361,9 @@ int64_t act_bwd_partial_floats(int64_t rows, int32_t d)
 }
 
 void launch_act_bwd(const float* g, const float* act, float* dy, int64_t rows, int32_t d,
-                    float* gb, float* partial, hipStream_t s)
+                    float* gb, float* partial, float scale, hipStream_t s)
 {
+    if (!act) scale = 1.f;
     if (rows <= 0) return;
     const int64_t blocks = (rows + kRowsPerBlockAct - 1) / kRowsPerBlockAct;
     if (!act && !gb) return;
@@ -308,25 +372,55 @@ void launch_act_bwd(const float* g, const float* act, float* dy, int64_t rows, i
                                      reinterpret_cast<uintptr_t>(partial)) & 15) == 0;
     if (vec)
         hipLaunchKernelGGL(k_act_bwd_vec, dim3((unsigned)blocks), dim3(kBlock), 0, s, g, act, dy, rows,
-                           d, partial);
+                           d, partial, scale);
     else
         hipLaunchKernelGGL(k_act_bwd, dim3((unsigned)blocks), dim3(kBlock), 0, s, g, act, dy, rows, d,
-                           partial);
+                           partial, scale);
     if (gb)
         hipLaunchKernelGGL(k_colsum_finish, dim3((unsigned)((d + 31) / 32)), dim3(kBlock),
                            0, s, (const float*)partial, blocks, d, gb);
 }
 
 void launch_act_bwd_bf16(const float* g, const void* act, void* dy, int64_t rows, int32_t d,
-                         float* gb, float* partial, hipStream_t s)
+                         float* gb, float* partial, float scale, hipStream_t s)
 {
     if (rows <= 0) return;
+    if (!act) scale = 1.f;
     const int64_t blocks = (rows + kRowsPerBlockAct - 1) / kRowsPerBlockAct;
     hipLaunchKernelGGL(k_act_bwd_bf16, dim3((unsigned)blocks), dim3(kBlock), 0, s, g,
-                       (const uint16_t*)act, (uint16_t*)dy, rows, d, partial);
+                       (const uint16_t*)act, (uint16_t*)dy, rows, d, partial, scale);
     if (gb)
         hipLaunchKernelGGL(k_colsum_finish, dim3((unsigned)((d + 31) / 32)), dim3(kBlock), 0, s,
                            (const float*)partial, blocks, d, gb);
+}
+
+void launch_dropout(void* a, int is_bf16, const int32_t* orig_of_row, int64_t rows, int32_t d,
+                    uint64_t key, uint32_t threshold, float scale, hipStream_t s)
+{
+    if (rows <= 0 || d <= 0) return;
+    int64_t blocks = (rows * d + kBlock - 1) / kBlock;
+    if (blocks > 65536) blocks = 65536;
+    if (is_bf16)
+        hipLaunchKernelGGL(k_dropout<uint16_t>, dim3((unsigned)blocks), dim3(kBlock), 0, s, (uint16_t*)a,
+                           orig_of_row, rows, d, (unsigned long long)key, threshold, scale);
+    else
+        hipLaunchKernelGGL(k_dropout<float>, dim3((unsigned)blocks), dim3(kBlock), 0, s, (float*)a,
+                           orig_of_row, rows, d, (unsigned long long)key, threshold, scale);
+}
+
+void launch_adam(float* w, const float* g, float* m, float* v, int64_t n, float lr, float beta1,
+                 float beta2, float eps, float weight_decay, float corr1, float corr2, hipStream_t s)
+{
+    if (n <= 0) return;
+    hipLaunchKernelGGL(k_adam, dim3((unsigned)((n + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, w, g, m, v,
+                       n, lr, beta1, beta2, eps, weight_decay, corr1, corr2);
+}
+
+void launch_sgd(float* w, const float* g, int64_t n, float lr, float weight_decay, hipStream_t s)
+{
+    if (n <= 0) return;
+    hipLaunchKernelGGL(k_sgd, dim3((unsigned)((n + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, w, g, n, lr,
+                       weight_decay);
 }
 
 }  // namespace gnnmi

@@ -102,7 +102,7 @@ CONFIGS = {
                  train_frac=0.5),
     # products-shaped: 2.4M nodes, ~62M undirected edges, 3-layer SAGE-mean
     "mid": dict(n=2_400_000, m_draw=70_500_000, seed=2, symmetric=True, self_loops=False,
-                model="sage", dims=(100, 256, 256, 47), dtype="f32", k=16, part="lp",
+                model="sage", dims=(100, 256, 256, 47), dtype="f32", k=16, part="switching",
                 train_frac=0.1),
     # half of papers100M's shape: 50M nodes, ~800M directed edges, 3-layer GCN
     "large": dict(n=50_000_000, m_draw=830_000_000, seed=3, symmetric=False, self_loops=True,

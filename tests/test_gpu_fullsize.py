@@ -3,6 +3,7 @@ entries, 3-layer SAGE-mean, k = 16 label-propagation partitions) in exactly the 
 configuration bench.py times, against one full fp64 oracle epoch on the host cores.
 
 Needs about 60 GB of host memory and roughly two minutes (most of it the oracle)."""
+import os
 import sys
 import time
 
@@ -49,8 +50,22 @@ def test_mid_workload_full_size(capsys):
 
     # partition structure: assignment bit-exact against the oracle's rule, boundary lists
     # against a vectorised restatement of the definition for every partition
-    want = op.assign_lp(rowptr, colidx, cfg["k"], cfg["seed"])
-    assert np.array_equal(part, want)
+    # (the switching-aware partitioner's assignment at this size is compared through the digest
+    # that tests/golden/make_switching_digest.py wrote from the oracle's partitioner alone)
+    if cfg["part"] == "lp":
+        want = op.assign_lp(rowptr, colidx, cfg["k"], cfg["seed"])
+        assert np.array_equal(part, want)
+    else:
+        import hashlib
+        fx = {}
+        for line in open(os.path.join(os.path.dirname(__file__), "golden", "mid_switching_digest.txt")):
+            if not line.startswith("#"):
+                key, *vals = line.split()
+                fx[key] = vals
+        assert cfg["part"] == "switching"
+        assert [int(fx["n"][0]), int(fx["k"][0]), int(fx["seed"][0])] == [n, cfg["k"], cfg["seed"]]
+        assert [int(x) for x in fx["sizes"]] == list(np.bincount(part, minlength=k))
+        assert hashlib.sha256(np.ascontiguousarray(part, dtype="<i4").tobytes()).hexdigest() == fx["sha256"][0]
     dst = np.repeat(np.arange(n, dtype=np.int32), np.diff(rowptr))
     cross = part[dst] != part[colidx]
     pair = np.unique(part[dst][cross].astype(np.int64) * n + colidx[cross])

@@ -399,3 +399,44 @@ def test_device_preference_counting_gives_the_host_partitioners_assignment(name,
     ih, oh = host.get_partitioner_history()
     idv, od = dev.get_partitioner_history()
     assert ih == idv and oh == od             # the objective is an exact integer on both sides
+
+
+@pytest.mark.parametrize("model,dims,dropout", [("sage", (12, 24, 24, 5), 0.3),
+                                                ("gcn", (12, 16, 16, 16, 16, 5), 0.5),     # 5 layers
+                                                ("gcn", (12, 24, 24, 5), 0.0)])
+def test_dropout_epoch_and_training_steps_match_oracle(model, dims, dropout):
+    say("case training %s %s dropout %g" % (model, dims, dropout))
+    n, k, seed = 1500, 5, 17
+    rowptr, colidx = small_graph(n, 9000, seed=3, symmetric=True, self_loops=False)
+    cfg = dict(model=model, dims=dims, seed=seed, train_frac=0.6)
+    X, y, m, w = make_inputs(cfg, n)
+    L = len(dims) - 1
+    from paper_2605_11517_amd import Session
+    s = Session(model, dims, rowptr, colidx, k, "switching", seed, X, w, y, m)
+    # one epoch with dropout, no step: every tensor against the oracle with the same draws
+    s.ctx.set_dropout(dropout, 99, 4)
+    loss = s.epoch()
+    got = s.results()
+    drop = None
+    if dropout > 0:
+        drop = [og.dropout_multipliers(n, dims[l + 1], dropout, 99, 4, l + 1) for l in range(L - 1)]
+        for l in range(L - 1):          # the same elements are dropped, bit for bit
+            dropped = drop[l] == 0
+            assert np.all(got["act"][l][dropped] == 0)
+    ref = og.epoch(model, rowptr, colidx, dims, X, w, y, m, drop=drop)
+    assert abs(loss - ref["loss"]) <= TOL * abs(ref["loss"])
+    compare(got, ref, model, tag="dropout epoch")
+    # three training epochs: losses and final weights
+    for opt, lr in (("adam", 0.01), ("sgd", 0.05)):
+        s = Session(model, dims, rowptr, colidx, k, "lp", seed, X, w, y, m)
+        losses = s.train(3, optimizer=opt, lr=lr, weight_decay=0.01, dropout=dropout, seed=7)
+        ref_losses, ref_w, _ = og.train(model, rowptr, colidx, dims, X, w, y, m, epochs=3, optimizer=opt,
+                                        lr=lr, weight_decay=0.01, dropout=dropout, seed=7)
+        for a, b in zip(losses, ref_losses):
+            assert abs(a - b) <= TOL * abs(b), (opt, losses, ref_losses)
+        gw = s.weights()
+        for l in range(L):
+            for name in ("W", "Ws", "b"):
+                if ref_w[l][name] is not None:
+                    assert rel_err(gw[l][name], ref_w[l][name]) <= TOL, (opt, l, name)
+        say("  %s losses %s" % (opt, ["%.5f" % x for x in losses]))
