@@ -243,6 +243,34 @@ gnn_status gnn_layer_bwd(gnn_ctx *ctx, int32_t layer, int32_t p, void *stream);
  * Synchronises `stream` before writing *loss_out (host). */
 gnn_status gnn_epoch(gnn_ctx *ctx, void *stream, float *loss_out);
 
+/* ---- layer order ------------------------------------------------------------------------ */
+
+/* The paper's layers aggregate the gathered rows and then transform them.  Aggregation and
+ * transform commute (S (A W) = (S A) W), so a layer whose output is narrower than its input
+ * moves fewer bytes when it transforms first: H = A^{l-1} W per partition, then gather,
+ * aggregate and scatter-accumulate at the output width, with no regather and no recompute in
+ * the backward pass (it needs only the partition's own rows of A^{l-1} and the gradient of H).
+ *   GNN_ORDER_AGGREGATE_FIRST (default): every layer as in the paper.
+ *   GNN_ORDER_AUTO: layers with d_l < d_{l-1} transform first (resident schedule, GNN_F32;
+ *     other layers and configurations keep the paper's order).
+ * Changes the workspace sizes: call before gnn_workspace_bytes / gnn_bind (a bound context
+ * becomes unbound).  Results differ from the other order only by rounding. */
+typedef enum { GNN_ORDER_AGGREGATE_FIRST = 0, GNN_ORDER_AUTO = 1 } gnn_layer_order;
+gnn_status gnn_set_layer_order(gnn_ctx *ctx, int32_t mode);
+gnn_status gnn_layer_is_transform_first(const gnn_ctx *ctx, int32_t layer, int32_t *out);
+
+/* Stepping a transform-first layer by hand (gnn_epoch does the same):
+ *   forward:  gnn_layer_transform_fwd(layer, p) for every p   (H_p = A_p^{l-1} W^l), then for
+ *             every p gnn_gather_boundary(layer, p) (gathers rows of H) and
+ *             gnn_layer_fwd(layer, p)  (A_p^l = act(S_p [H_own ; staging] (+ A_p^{l-1} W_s) + b));
+ *   backward: gnn_layer_bwd(layer, p) for every p, without a gather (dY_p, grad b, grad W_s,
+ *             grad A^{l-1}_own += dY_p W_s^T, grad H [R_p] += S_p^T dY_p), then
+ *             gnn_layer_transform_bwd(layer, p) for every p (grad W += A_p^{l-1 T} grad H_p,
+ *             grad A^{l-1}_own += grad H_p W^T) before layer-1 starts.
+ * GNN_ESTATE when the layer aggregates first or a sweep is incomplete. */
+gnn_status gnn_layer_transform_fwd(gnn_ctx *ctx, int32_t layer, int32_t p, void *stream);
+gnn_status gnn_layer_transform_bwd(gnn_ctx *ctx, int32_t layer, int32_t p, void *stream);
+
 /* ---- training around the epoch (datasets table: learning rate, dropout, epochs) ---------- */
 
 /* Dropout with rate p in [0, 1) after the activation of every hidden layer in the epochs

@@ -89,6 +89,10 @@ def load_library():
         "gnn_read_loss": [vp, vp, P(C.c_float)],
         "gnn_layer_bwd": [vp, i32, i32, vp],
         "gnn_epoch": [vp, vp, P(C.c_float)],
+        "gnn_set_layer_order": [vp, i32],
+        "gnn_layer_is_transform_first": [vp, i32, P(i32)],
+        "gnn_layer_transform_fwd": [vp, i32, i32, vp],
+        "gnn_layer_transform_bwd": [vp, i32, i32, vp],
         "gnn_set_dropout": [vp, C.c_float, u64, i64],
         "gnn_bind_optimizer": [vp, P(vp), P(vp)],
         "gnn_optimizer_step": [vp, P(Optimizer), i64, vp],
@@ -240,6 +244,20 @@ class Context:
         self._check(self.lib.gnn_epoch(self.h, stream, C.byref(v)))
         return float(v.value)
 
+    def set_layer_order(self, mode):
+        self._check(self.lib.gnn_set_layer_order(self.h, {"aggregate": 0, "auto": 1}[mode]))
+
+    def layer_is_transform_first(self, layer):
+        out = C.c_int32()
+        self._check(self.lib.gnn_layer_is_transform_first(self.h, layer, C.byref(out)))
+        return bool(out.value)
+
+    def layer_transform_fwd(self, layer, p, stream):
+        self._check(self.lib.gnn_layer_transform_fwd(self.h, layer, p, stream))
+
+    def layer_transform_bwd(self, layer, p, stream):
+        self._check(self.lib.gnn_layer_transform_bwd(self.h, layer, p, stream))
+
     def set_dropout(self, p, seed, epoch_index):
         self._check(self.lib.gnn_set_dropout(self.h, float(p), int(seed), int(epoch_index)))
 
@@ -282,7 +300,7 @@ class Session:
 
     def __init__(self, model, dims, rowptr, colidx, k, part_mode, seed, X, weights, labels,
                  train_mask, has_bias=True, user_part=None, device="cuda:0", dtype="f32",
-                 hbm_budget_bytes=0):
+                 hbm_budget_bytes=0, layer_order="aggregate"):
         import torch
         self.torch = torch
         if not torch.cuda.is_available():
@@ -295,6 +313,7 @@ class Session:
         self.streaming = hbm_budget_bytes != 0
         self.ctx = Context(model, dims, dtype=GNN_BF16 if self.bf16 else GNN_F32, has_bias=has_bias,
                            hbm_budget_bytes=hbm_budget_bytes)
+        self.ctx.set_layer_order(layer_order)
         self.ctx.build_partitions(rowptr, colidx, k, part_mode, seed, user_part)
         self.model = _MODEL.get(model, model)
         self.dims = list(dims)

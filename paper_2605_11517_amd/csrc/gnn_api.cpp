@@ -124,6 +124,14 @@ void compute_workspace(gnn_ctx* c)
     w.losspart = take(loss_partial_floats(M.n, M.k));
     w.scalars = take(64);
     w.segpart = take(std::max(M.plan_fwd.max_segs, M.plan_bwd.max_segs) * din);
+    int64_t hp = 0;
+    for (int32_t l = 1; l <= L; ++l)
+        if (c->transform_first(l)) hp = std::max<int64_t>(hp, c->padded(l));
+    w.h = w.gh = 0;
+    if (hp > 0) {
+        w.h = take(M.n * hp);
+        w.gh = take(M.n * hp);
+    }
     w.scratch_bytes = o;
 }
 
@@ -358,6 +366,117 @@ void compute_bwd_self(gnn_ctx* c, int32_t layer, int32_t p, const char* dY, floa
     else launch_gemm_nt((const float*)dY, dout, (const float*)Ws, dout, gprev_own, din, np, din, dout, ep, s);
 }
 
+
+static int32_t all_done(const std::vector<uint8_t>& flags, int32_t layer, int32_t k)
+{
+    int32_t cnt = 0;
+    for (int32_t q = 0; q < k; ++q) cnt += flags[(size_t)(layer - 1) * (size_t)k + (size_t)q] ? 1 : 0;
+    return cnt;
+}
+
+// Transform-first layer, forward of partition p after H = A^{l-1} W exists for every vertex:
+// Z = S_p [H_own ; staging], A_p^l = act(Z (+ A_p^{l-1} W_s) + b).
+static void xf_aggregate_fwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
+{
+    const HostMeta& M = c->M;
+    const int64_t r0 = M.off[(size_t)p], np = M.off[(size_t)p + 1] - r0;
+    const int32_t din = c->dims[(size_t)layer - 1], dout = c->dims[(size_t)layer], dp = c->padded(layer);
+    const SpmmItems items = plan_items(M.plan_fwd, c->D.fwd, p);
+    const float* rscale = c->D.rscale ? c->D.rscale + r0 : nullptr;
+    float* Z = (float*)(c->scratch + c->ws.z);
+    float* segpart = (float*)(c->scratch + c->ws.segpart);
+    const float* H = (const float*)(c->scratch + c->ws.h) + r0 * dp;
+    {
+        Timed t(c, s, GNN_K_SPMM);
+        launch_spmm(c->D.rp + r0, c->D.lcol, c->D.ew, rscale, H, np, c->staging, Z, np, dp, 0, 0, items,
+                    segpart, 1, SpmmScatter{}, s);
+    }
+    if (items.nlong > 0) {
+        Timed t(c, s, GNN_K_SPMM_REDUCE);
+        launch_spmm_reduce(rscale, Z, dp, 0, items, segpart, SpmmScatter{}, s);
+    }
+    float* out = (float*)c->act[(size_t)layer - 1] + r0 * dout;
+    const float* bias = c->has_bias ? (const float*)c->w[(size_t)3 * (layer - 1) + 2] : nullptr;
+    const int relu = layer < c->L ? 1 : 0;
+    Timed t(c, s, GNN_K_GEMM_FWD);
+    if (c->model == GNN_SAGE_MEAN) {
+        GemmSeg seg;
+        seg.a = (const float*)c->layer_input(layer, r0); seg.lda = din;
+        seg.b = (const float*)c->w[(size_t)3 * (layer - 1) + 1]; seg.ldb = dout; seg.k = din;
+        GemmEpilogue ep;
+        ep.bias = bias;
+        launch_gemm_nn(&seg, 1, out, dout, np, dout, ep, s);
+        launch_add_padded(out, Z, np, dout, dp, nullptr, 1, relu, s);
+    } else {
+        launch_add_padded(out, Z, np, dout, dp, bias, 0, relu, s);
+    }
+    if (c->dropout_p > 0.f && layer < c->L) {
+        const uint64_t key = splitmix64(c->dropout_seed ^ splitmix64((uint64_t)(64 * c->dropout_epoch + layer)));
+        const uint32_t threshold = (uint32_t)std::floor((double)c->dropout_p * 4294967296.0);
+        launch_dropout(out, 0, c->D.order + r0, np, dout, key, threshold, 1.f / (1.f - c->dropout_p), s);
+    }
+}
+
+// Transform-first layer, backward of partition p: dY_p, bias and self-weight gradients, and
+// grad H [R_p] += S_p^T dY_p (the scatter-accumulate happens at the layer's output width).
+static void xf_aggregate_bwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
+{
+    const HostMeta& M = c->M;
+    const int32_t L = c->L;
+    const int64_t r0 = M.off[(size_t)p], np = M.off[(size_t)p + 1] - r0;
+    const int64_t nb = M.boff[(size_t)p + 1] - M.boff[(size_t)p];
+    const int32_t din = c->dims[(size_t)layer - 1], dout = c->dims[(size_t)layer], dp = c->padded(layer);
+    float* gb = c->has_bias ? c->gw[(size_t)3 * (layer - 1) + 2] : nullptr;
+    float* dYbuf = (float*)(c->scratch + c->ws.dy);
+    float* colpart = (float*)(c->scratch + c->ws.colpart);
+    const float* g_own = c->gact[(size_t)layer - 1] + r0 * dout;
+    const float drop_scale = c->dropout_p > 0.f ? 1.f / (1.f - c->dropout_p) : 1.f;
+    const float* dY = g_own;
+    {
+        Timed t(c, s, GNN_K_ACT_BWD);
+        if (layer < L) {
+            launch_act_bwd(g_own, (const float*)c->act[(size_t)layer - 1] + r0 * dout, dYbuf, np, dout, gb,
+                           colpart, drop_scale, s);
+            dY = dYbuf;
+        } else {
+            launch_act_bwd(g_own, nullptr, nullptr, np, dout, gb, colpart, 1.f, s);
+        }
+    }
+    const float* in_own = (const float*)c->layer_input(layer, r0);
+    if (c->model == GNN_SAGE_MEAN) {
+        {
+            Timed t(c, s, GNN_K_GEMM_DW);
+            launch_gemm_tn(in_own, din, dY, dout, c->gw[(size_t)3 * (layer - 1) + 1], dout, din, dout, np,
+                           (float*)(c->scratch + c->ws.partial), s);
+        }
+        if (layer >= 2) compute_bwd_self(c, layer, p, (const char*)dY, c->gact[(size_t)layer - 2] + r0 * din, s);
+    }
+    const float* dYp = dY;
+    if (dp != dout) {
+        Timed t(c, s, GNN_K_OTHER);
+        float* pad = (float*)(c->scratch + c->ws.dz);
+        launch_pad_rows(pad, dY, np, dout, dp, s);
+        dYp = pad;
+    }
+    const int64_t t0 = M.toff[(size_t)p];
+    const SpmmItems items = plan_items(M.plan_bwd, c->D.bwd, p);
+    float* segpart = (float*)(c->scratch + c->ws.segpart);
+    SpmmScatter sc;
+    sc.n_own = np;
+    sc.base_row = r0;
+    sc.idx = c->D.bnd + M.boff[(size_t)p];
+    float* gH = (float*)(c->scratch + c->ws.gh);
+    {
+        Timed t(c, s, GNN_K_SPMM_T);
+        launch_spmm(c->D.trp + t0, c->D.tcol, c->D.tw, nullptr, dYp, np, nullptr, gH, np + nb, dp, 0, 0, items,
+                    segpart, 0, sc, s);
+    }
+    if (items.nlong > 0) {
+        Timed t(c, s, GNN_K_SPMM_REDUCE);
+        launch_spmm_reduce(nullptr, gH, dp, 0, items, segpart, sc, s);
+    }
+}
+
 }  // namespace gnnmi
 
 // =================================================================================================
@@ -424,6 +543,8 @@ gnn_status gnn_build_partitions(gnn_ctx* c, int64_t n, const int64_t* rowptr, co
     c->staged_layer = c->staged_p = -1;
     c->loss_done = false;
     c->fwd_done.assign((size_t)c->L * (size_t)k, 0);
+    c->xf_fwd_done.assign((size_t)c->L * (size_t)k, 0);
+    c->xf_bwd_done.assign((size_t)c->L * (size_t)k, 0);
     c->bwd_done.assign((size_t)c->L + 2, 0);
     compute_workspace(c);
     return GNN_OK;
@@ -536,6 +657,8 @@ gnn_status gnn_bind(gnn_ctx* c, const void* feat, void* const* act, void* const*
     c->staged_layer = c->staged_p = -1;
     c->loss_done = false;
     std::fill(c->fwd_done.begin(), c->fwd_done.end(), 0);
+    std::fill(c->xf_fwd_done.begin(), c->xf_fwd_done.end(), 0);
+    std::fill(c->xf_bwd_done.begin(), c->xf_bwd_done.end(), 0);
     std::fill(c->bwd_done.begin(), c->bwd_done.end(), 0);
     if (c->streaming()) {
         st = stream_engine_create(c);
@@ -567,8 +690,14 @@ gnn_status gnn_gather_boundary(gnn_ctx* c, int32_t layer, int32_t p, void* strea
     hipStream_t s = (hipStream_t)stream;
     const HostMeta& M = c->M;
     const int64_t b0 = M.boff[(size_t)p], nb = M.boff[(size_t)p + 1] - b0;
-    const int64_t row_bytes = (int64_t)c->dims[(size_t)layer - 1] * c->es();
-    {
+    if (c->transform_first(layer)) {
+        // the layer aggregates H = A^{l-1} W: every partition's rows of H must exist
+        if (all_done(c->xf_fwd_done, layer, M.k) < M.k)
+            return c->fail(GNN_ESTATE, "transform-first layer: gnn_layer_transform_fwd has not covered every partition");
+        Timed t(c, s, GNN_K_GATHER);
+        launch_gather_rows(c->scratch + c->ws.h, c->D.bnd + b0, c->staging, nb, (int64_t)c->padded(layer) * 4, s);
+    } else {
+        const int64_t row_bytes = (int64_t)c->dims[(size_t)layer - 1] * c->es();
         Timed t(c, s, GNN_K_GATHER);
         launch_gather_rows(c->layer_input(layer), c->D.bnd + b0, c->staging, nb, row_bytes, s);
     }
@@ -587,10 +716,89 @@ gnn_status gnn_layer_fwd(gnn_ctx* c, int32_t layer, int32_t p, void* stream)
     hipStream_t s = (hipStream_t)stream;
     const int64_t r0 = c->M.off[(size_t)p];
     const int32_t dout = c->dims[(size_t)layer];
-    compute_fwd(c, layer, p, c->layer_input(layer, r0),
-                c->act[(size_t)layer - 1] + r0 * (int64_t)dout * c->act_es(layer), s);
+    if (c->transform_first(layer))
+        xf_aggregate_fwd(c, layer, p, s);
+    else
+        compute_fwd(c, layer, p, c->layer_input(layer, r0),
+                    c->act[(size_t)layer - 1] + r0 * (int64_t)dout * c->act_es(layer), s);
     c->fwd_done[(size_t)(layer - 1) * (size_t)c->M.k + (size_t)p] = 1;
     return check_launch(c, "gnn_layer_fwd");
+}
+
+gnn_status gnn_set_layer_order(gnn_ctx* c, int32_t mode)
+{
+    if (!c) return GNN_EINVAL;
+    if (mode != GNN_ORDER_AGGREGATE_FIRST && mode != GNN_ORDER_AUTO)
+        return c->fail(GNN_EINVAL, "unknown layer order");
+    c->order_mode = mode;
+    c->bound = false;              // workspace sizes depend on the order
+    if (c->built) compute_workspace(c);
+    return GNN_OK;
+}
+
+gnn_status gnn_layer_is_transform_first(const gnn_ctx* c, int32_t layer, int32_t* out)
+{
+    if (!c || !out) return GNN_EINVAL;
+    if (layer < 1 || layer > c->L) return c->fail(GNN_EINVAL, "layer outside 1..L");
+    *out = c->transform_first(layer) ? 1 : 0;
+    return GNN_OK;
+}
+
+gnn_status gnn_layer_transform_fwd(gnn_ctx* c, int32_t layer, int32_t p, void* stream)
+{
+    if (!c) return GNN_EINVAL;
+    gnn_status st = check_lp(c, layer, p);
+    if (st != GNN_OK) return st;
+    if (!c->transform_first(layer)) return c->fail(GNN_ESTATE, "this layer aggregates first");
+    hipStream_t s = (hipStream_t)stream;
+    const HostMeta& M = c->M;
+    const int64_t r0 = M.off[(size_t)p], np = M.off[(size_t)p + 1] - r0;
+    const int32_t din = c->dims[(size_t)layer - 1], dout = c->dims[(size_t)layer], dp = c->padded(layer);
+    float* H = (float*)(c->scratch + c->ws.h) + r0 * dp;
+    if (dp != dout) {
+        // columns dout..dp of H are read by the aggregation as part of whole vectors
+        Timed t(c, s, GNN_K_OTHER);
+        launch_fill_zero(H, np * (int64_t)dp * 4, s);
+    }
+    {
+        Timed t(c, s, GNN_K_GEMM_FWD);
+        GemmSeg seg;
+        seg.a = (const float*)c->layer_input(layer, r0); seg.lda = din;
+        seg.b = (const float*)c->w[(size_t)3 * (layer - 1)]; seg.ldb = dout; seg.k = din;
+        launch_gemm_nn(&seg, 1, H, dp, np, dout, GemmEpilogue{}, s);
+    }
+    c->xf_fwd_done[(size_t)(layer - 1) * (size_t)M.k + (size_t)p] = 1;
+    return check_launch(c, "gnn_layer_transform_fwd");
+}
+
+gnn_status gnn_layer_transform_bwd(gnn_ctx* c, int32_t layer, int32_t p, void* stream)
+{
+    if (!c) return GNN_EINVAL;
+    gnn_status st = check_lp(c, layer, p);
+    if (st != GNN_OK) return st;
+    if (!c->transform_first(layer)) return c->fail(GNN_ESTATE, "this layer aggregates first");
+    if (!c->loss_done || c->bwd_done[(size_t)layer] < c->M.k)
+        return c->fail(GNN_ESTATE, "gnn_layer_bwd of this layer has not covered every partition");
+    hipStream_t s = (hipStream_t)stream;
+    const HostMeta& M = c->M;
+    const int64_t r0 = M.off[(size_t)p], np = M.off[(size_t)p + 1] - r0;
+    const int32_t din = c->dims[(size_t)layer - 1], dout = c->dims[(size_t)layer], dp = c->padded(layer);
+    const float* gH = (const float*)(c->scratch + c->ws.gh) + r0 * dp;
+    const float* in_own = (const float*)c->layer_input(layer, r0);
+    {
+        Timed t(c, s, GNN_K_GEMM_DW);
+        launch_gemm_tn(in_own, din, gH, dp, c->gw[(size_t)3 * (layer - 1)], dout, din, dout, np,
+                       (float*)(c->scratch + c->ws.partial), s);
+    }
+    if (layer >= 2) {
+        Timed t(c, s, GNN_K_GEMM_DZ);
+        GemmEpilogue ep;
+        ep.accumulate = 1;
+        launch_gemm_nt(gH, dp, (const float*)c->w[(size_t)3 * (layer - 1)], dout,
+                       c->gact[(size_t)layer - 2] + r0 * din, din, np, din, dout, ep, s);
+    }
+    c->xf_bwd_done[(size_t)(layer - 1) * (size_t)M.k + (size_t)p] = 1;
+    return check_launch(c, "gnn_layer_transform_bwd");
 }
 
 gnn_status gnn_loss(gnn_ctx* c, void* stream)
@@ -633,9 +841,24 @@ gnn_status gnn_layer_bwd(gnn_ctx* c, int32_t layer, int32_t p, void* stream)
     if (!c->loss_done) return c->fail(GNN_ESTATE, "gnn_layer_bwd before the forward pass and gnn_loss");
     if (layer < c->L && c->bwd_done[(size_t)layer + 1] < c->M.k)
         return c->fail(GNN_ESTATE, "the backward pass of layer+1 has not covered every partition");
+    if (layer < c->L && c->transform_first(layer + 1) && all_done(c->xf_bwd_done, layer + 1, c->M.k) < c->M.k)
+        return c->fail(GNN_ESTATE, "gnn_layer_transform_bwd of layer+1 has not covered every partition");
+    hipStream_t s = (hipStream_t)stream;
+    if (c->transform_first(layer)) {
+        // no regather and no recompute: the layer aggregated H, whose gradient is accumulated here
+        if (c->bwd_done[(size_t)layer] == 0) {
+            Timed t(c, s, GNN_K_OTHER);
+            launch_fill_zero(c->scratch + c->ws.gh, c->M.n * (int64_t)c->padded(layer) * 4, s);
+            if (layer >= 2)
+                launch_fill_zero(c->gact[(size_t)layer - 2], c->M.n * (int64_t)c->dims[(size_t)layer - 1] * 4, s);
+            for (int32_t q = 0; q < c->M.k; ++q) c->xf_bwd_done[(size_t)(layer - 1) * (size_t)c->M.k + (size_t)q] = 0;
+        }
+        xf_aggregate_bwd(c, layer, p, s);
+        c->bwd_done[(size_t)layer] += 1;
+        return check_launch(c, "gnn_layer_bwd");
+    }
     if (c->staged_layer != layer || c->staged_p != p)
         return c->fail(GNN_ESTATE, "staging does not hold this (layer, partition); call gnn_gather_boundary first");
-    hipStream_t s = (hipStream_t)stream;
     const HostMeta& M = c->M;
     const int64_t r0 = M.off[(size_t)p], np = M.off[(size_t)p + 1] - r0;
     const int64_t nb = M.boff[(size_t)p + 1] - M.boff[(size_t)p];
@@ -682,19 +905,28 @@ gnn_status gnn_epoch(gnn_ctx* c, void* stream, float* loss_out)
     }
     gnn_status st;
     zero_weight_grads(c, s);
-    for (int32_t l = 1; l <= L; ++l)
+    for (int32_t l = 1; l <= L; ++l) {
+        if (c->transform_first(l))
+            for (int32_t t = 0; t < k; ++t)
+                if ((st = gnn_layer_transform_fwd(c, l, c->M.sched[(size_t)t], stream)) != GNN_OK) return st;
         for (int32_t t = 0; t < k; ++t) {
             const int32_t p = c->M.sched[(size_t)t];
             if ((st = gnn_gather_boundary(c, l, p, stream)) != GNN_OK) return st;
             if ((st = gnn_layer_fwd(c, l, p, stream)) != GNN_OK) return st;
         }
+    }
     if ((st = gnn_loss(c, stream)) != GNN_OK) return st;
-    for (int32_t l = L; l >= 1; --l)
+    for (int32_t l = L; l >= 1; --l) {
+        const bool xf = c->transform_first(l);
         for (int32_t t = 0; t < k; ++t) {
             const int32_t p = c->M.sched[(size_t)t];
-            if ((st = gnn_gather_boundary(c, l, p, stream)) != GNN_OK) return st;
+            if (!xf && (st = gnn_gather_boundary(c, l, p, stream)) != GNN_OK) return st;
             if ((st = gnn_layer_bwd(c, l, p, stream)) != GNN_OK) return st;
         }
+        if (xf)
+            for (int32_t t = 0; t < k; ++t)
+                if ((st = gnn_layer_transform_bwd(c, l, c->M.sched[(size_t)t], stream)) != GNN_OK) return st;
+    }
     if ((st = gnn_read_loss(c, stream, loss_out)) != GNN_OK) return st;
     if (c->prof) collect_profile(c);
     return GNN_OK;

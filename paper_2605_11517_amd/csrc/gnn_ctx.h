@@ -37,6 +37,7 @@ struct DevMeta {
 struct Workspace {  // byte offsets into `scratch`
     int64_t z = 0, dy = 0, dz = 0, dga = 0, partial = 0, colpart = 0, losspart = 0, scalars = 0,
             segpart = 0;
+    int64_t h = 0, gh = 0;     // transform-first layers: H = A W and its gradient, n x padded width
     int64_t staging_bytes = 0, scratch_bytes = 0;
 };
 
@@ -68,6 +69,17 @@ struct gnn_ctx {
     const uint8_t* mask = nullptr;
     char* staging = nullptr;
     char* scratch = nullptr;
+    // layer order: 0 = aggregate, then transform (the paper's); 1 = transform first in layers
+    // that narrow (resident schedule, fp32)
+    int32_t order_mode = 0;
+    bool transform_first(int32_t layer) const
+    {
+        return order_mode == 1 && !streaming() && !bf16() &&
+               dims[(size_t)layer] < dims[(size_t)layer - 1];
+    }
+    // width of H rows: d_layer rounded up to whole 16-byte vectors
+    int32_t padded(int32_t layer) const { return (dims[(size_t)layer] + 3) / 4 * 4; }
+    std::vector<uint8_t> xf_fwd_done, xf_bwd_done;   // L * k: transform sweeps of such layers
     // schedule state
     int32_t staged_layer = -1, staged_p = -1;
     std::vector<uint8_t> fwd_done;      // L * k

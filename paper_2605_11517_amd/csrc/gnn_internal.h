@@ -200,6 +200,12 @@ void launch_loss_finish(const float* partial, int64_t nparts, const unsigned lon
 
 void launch_fill_zero(void* p, int64_t bytes, hipStream_t s);
 
+// Transform-first layers: out = (accumulate ? out : 0) + z[:, :d] (+ bias), optional relu, with
+// z's row stride ldz >= d; and a row copy into a wider, zero-padded row.
+void launch_add_padded(float* out, const float* z, int64_t rows, int32_t d, int32_t ldz,
+                       const float* bias, int accumulate, int relu, hipStream_t s);
+void launch_pad_rows(float* dst, const float* src, int64_t rows, int32_t d, int32_t ld, hipStream_t s);
+
 // Training pieces: dropout on a block of activation rows (orig_of_row[r] = original vertex id
 // of row r), and the optimizer steps on one fp32 parameter tensor.
 void launch_dropout(void* a, int is_bf16, const int32_t* orig_of_row, int64_t rows, int32_t d,

@@ -290,6 +290,40 @@ __global__ __launch_bounds__(kBlock) void k_dropout(T* __restrict__ a, const int
     }
 }
 
+// Epilogue of a transform-first layer: out[r, j] = (accumulate ? out[r, j] : 0) + z[r, j]
+// (+ bias[j]), then the activation.  z has row stride ldz >= d (padded to whole 16-byte
+// vectors for the aggregation), out has row stride d.
+__global__ __launch_bounds__(kBlock) void k_add_padded(float* __restrict__ out, const float* __restrict__ z,
+                                                       int64_t rows, int32_t d, int32_t ldz,
+                                                       const float* __restrict__ bias, int accumulate,
+                                                       int relu)
+{
+    const int64_t total = rows * d;
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < total;
+         i += (int64_t)gridDim.x * kBlock) {
+        const int64_t r = i / d;
+        const int32_t j = (int32_t)(i - r * d);
+        float v = z[r * ldz + j];
+        if (accumulate) v += out[i];
+        if (bias) v += bias[j];
+        if (relu) v = v > 0.f ? v : 0.f;
+        out[i] = v;
+    }
+}
+
+// dst[r, 0..ld) = src[r, 0..d) followed by zeros (ld >= d)
+__global__ __launch_bounds__(kBlock) void k_pad_rows(float* __restrict__ dst, const float* __restrict__ src,
+                                                     int64_t rows, int32_t d, int32_t ld)
+{
+    const int64_t total = rows * ld;
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < total;
+         i += (int64_t)gridDim.x * kBlock) {
+        const int64_t r = i / ld;
+        const int32_t j = (int32_t)(i - r * ld);
+        dst[i] = j < d ? src[r * d + j] : 0.f;
+    }
+}
+
 // One optimizer step over a parameter tensor of n floats.
 __global__ __launch_bounds__(kBlock) void k_adam(float* __restrict__ w, const float* __restrict__ g,
                                                  float* __restrict__ m, float* __restrict__ v, int64_t n,
@@ -406,6 +440,24 @@ void launch_dropout(void* a, int is_bf16, const int32_t* orig_of_row, int64_t ro
     else
         hipLaunchKernelGGL(k_dropout<float>, dim3((unsigned)blocks), dim3(kBlock), 0, s, (float*)a,
                            orig_of_row, rows, d, (unsigned long long)key, threshold, scale);
+}
+
+void launch_add_padded(float* out, const float* z, int64_t rows, int32_t d, int32_t ldz,
+                       const float* bias, int accumulate, int relu, hipStream_t s)
+{
+    if (rows <= 0 || d <= 0) return;
+    int64_t blocks = (rows * d + kBlock - 1) / kBlock;
+    if (blocks > 65536) blocks = 65536;
+    hipLaunchKernelGGL(k_add_padded, dim3((unsigned)blocks), dim3(kBlock), 0, s, out, z, rows, d, ldz, bias,
+                       accumulate, relu);
+}
+
+void launch_pad_rows(float* dst, const float* src, int64_t rows, int32_t d, int32_t ld, hipStream_t s)
+{
+    if (rows <= 0 || ld <= 0) return;
+    int64_t blocks = (rows * ld + kBlock - 1) / kBlock;
+    if (blocks > 65536) blocks = 65536;
+    hipLaunchKernelGGL(k_pad_rows, dim3((unsigned)blocks), dim3(kBlock), 0, s, dst, src, rows, d, ld);
 }
 
 void launch_adam(float* w, const float* g, float* m, float* v, int64_t n, float lr, float beta1,
