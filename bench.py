@@ -29,17 +29,26 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def algorithmic_bytes(stats, dims, model, n_parts, es=4, fused_scatter=False):
+def algorithmic_bytes(stats, dims, model, n_parts, es=4, fused_scatter=False, xf=None):
     """HBM bytes the method has to move per epoch, by kernel class (lower bound: every needed
     source row is read once per partition).  es = bytes per stored activation (4 fp32, 2 bf16);
-    gradients of activations are always fp32."""
+    gradients of activations are always fp32.  xf[l-1]: layer l transforms first, so it
+    gathers, aggregates and scatter-accumulates rows of its (padded) output width, once
+    forward and once backward, with no regather and no recompute."""
     n, nnz, k = stats["n"], stats["nnz"], stats["k"]
     sum_r = n + stats["sum_boundary"]            # sum over partitions of |own_p| + |B_p|
     sum_b = stats["sum_boundary"]
     L = len(dims) - 1
     per_entry = 4 + (4 if model == "gcn" else 0)  # column index (+ stored weight for GCN)
     out = {"gather": 0, "spmm": 0, "spmm_t": 0, "scatter": 0}
+    xf = xf or [False] * L
     for l in range(1, L + 1):
+        if xf[l - 1]:
+            row = (dims[l] + 3) // 4 * 4 * 4
+            out["gather"] += 2 * sum_b * row + 4 * sum_b
+            out["spmm"] += per_entry * nnz + 8 * (n + k) + sum_r * row + n * row + (4 * n if model == "sage" else 0)
+            out["spmm_t"] += 8 * nnz + 8 * (sum_r + k) + n * row + 2 * sum_r * row + 4 * sum_b
+            continue
         d = dims[l - 1]
         row = d * es
         grow = d * 4
@@ -112,6 +121,11 @@ def main():
     ap.add_argument("--workload", default="mid")
     ap.add_argument("--cpu-sample-n", type=int, default=0, help="vertices of the oracle sample (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--partitioner", choices=["random", "lp", "switching", "switching_device"], default=None,
+                    help="override the workload's partitioner")
+    ap.add_argument("--layer-order", choices=["auto", "aggregate"], default="auto",
+                    help="auto: layers that narrow transform first (same results up to rounding, "
+                         "fewer bytes); aggregate: every layer aggregates first, as in the paper")
     ap.add_argument("--hbm-budget-gb", type=float, default=0.0,
                     help="> 0: run the streaming schedule (activations and gradients in pinned host "
                          "memory) with this much HBM for the partition-block caches")
@@ -141,8 +155,12 @@ def main():
     y, m = labels_and_mask(n, dims[-1], cfg["train_frac"], cfg["seed"])
     w = glorot_weights(dims, cfg["seed"], sage=(model == "sage"))
     t1 = time.perf_counter()
+    if args.partitioner:
+        cfg["part"] = args.partitioner
     s = Session(model, dims, rowptr, colidx, cfg["k"], cfg["part"], cfg["seed"], X, w, y, m,
-                dtype=cfg["dtype"], hbm_budget_bytes=int(args.hbm_budget_gb * 2 ** 30))
+                dtype=cfg["dtype"], hbm_budget_bytes=int(args.hbm_budget_gb * 2 ** 30),
+                layer_order=args.layer_order)
+    xf = [s.ctx.layer_is_transform_first(l) for l in range(1, len(dims))]
     es = 2 if cfg["dtype"] == "bf16" else 4
     mfma_peak = MFMA_BF16_PEAK_TFLOPS if cfg["dtype"] == "bf16" else MFMA_F32_PEAK_TFLOPS
     stats = s.ctx.get_stats()
@@ -191,12 +209,13 @@ def main():
                                                  " (streaming, %.3g GiB block cache)" % args.hbm_budget_gb),
                    "n": n, "operator_entries": nnz, "model": model,
                    "dims": list(dims), "k": stats["k"], "partitioner": cfg["part"],
-                   "alpha": stats["sum_required"] / n, "sum_boundary": stats["sum_boundary"]},
+                   "alpha": stats["sum_required"] / n, "sum_boundary": stats["sum_boundary"],
+                   "layer_order": ["transform-first" if t else "aggregate-first" for t in xf]},
         "loss": loss,
     }
     if prof:
         ab = algorithmic_bytes(stats, dims, model, stats["k"], es,
-                               fused_scatter=prof.get("scatter", (0, 0))[1] == 0)
+                               fused_scatter=prof.get("scatter", (0, 0))[1] == 0, xf=xf)
         fl = gemm_flops(stats, dims, model)
         classes = {}
         for name, (ms, launches) in prof.items():
@@ -210,9 +229,10 @@ def main():
             classes[name] = e
         out["kernel_classes"] = classes
         sp_ms, sp_launches = prof["spmm"]
-        passes = 2 * (len(dims) - 1)
+        passes = sum(1 if t else 2 for t in xf)       # forward (+ recompute) aggregations
         tp_ms = prof["spmm_t"][0]
-        out["aggregated_edges_per_s"] = nnz * (passes + len(dims) - 2) * args.steps / ((sp_ms + tp_ms) * 1e-3)
+        transposed = (len(dims) - 2) + (1 if xf[0] else 0)   # a transform-first layer 1 still pushes grad H
+        out["aggregated_edges_per_s"] = nnz * (passes + transposed) * args.steps / ((sp_ms + tp_ms) * 1e-3)
         # dominant kernel: k_spmm_items, every launch of it (forward, recompute and transposed)
         k_ms = sp_ms + tp_ms
         k_launches = sp_launches + prof["spmm_t"][1]
@@ -229,8 +249,13 @@ def main():
                 tot_l = sum(r["launches"] for r in rows)
                 traffic = sum(r["bytes_per_launch"] * r["launches"] for r in rows) / tot_l
         L = len(dims) - 1
-        upper = sum((2 if l == 0 else 3) * (stats["nnz"] * (4 + dims[l] * es) + n * dims[l] * es)
-                    for l in range(L))
+        upper = 0
+        for l in range(L):
+            if xf[l]:
+                roww = (dims[l + 1] + 3) // 4 * 4 * 4
+                upper += 2 * (stats["nnz"] * (4 + roww) + n * roww)
+            else:
+                upper += (2 if l == 0 else 3) * (stats["nnz"] * (4 + dims[l] * es) + n * dims[l] * es)
         out["roofline"] = {
             "kernel": "k_spmm_slots / k_spmm_items (aggregation over T_p and T_p^T: forward, recompute, "
                       "transposed; column-sliced variant where rows are whole 128-byte lines)",

@@ -1,0 +1,128 @@
+"""Full-graph graph-attention (GAT) layers: forward, loss and backward in fp64 numpy.
+
+TEST INFRASTRUCTURE ONLY (see ``oracle/__init__.py``).
+
+The paper evaluates GAT as a second model family and notes that attention needs the gathered
+inputs themselves in the backward pass (section on grad-engine activation regathering); it
+does not restate the layer, so the definition is the published one (Velickovic et al., "Graph
+Attention Networks", one head), as PyG's ``GATConv`` computes it:
+
+    H = A^{l-1} W                                   [n, f]
+    e(u -> v) = LeakyReLU_0.2(a_src . H[u] + a_dst . H[v])      for u in N(v) + {v}
+    alpha(u -> v) = softmax over the sources u of v
+    Z[v] = sum_u alpha(u -> v) H[u];   A^l = act(Z + b),  act = ReLU on hidden layers
+
+``N(v)`` is row ``v`` of the CSR (sources of v) and every vertex gets exactly one self-loop,
+as in the GCN operator.  Everything is written per edge with plain numpy gathers and
+``np.add.at`` scatters, in the order of the formulas.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from . import fullgraph
+
+SLOPE = 0.2
+
+
+def edges_with_self_loops(rowptr, colidx):
+    """(dst, src) arrays of the attention graph: the CSR's entries plus one self-loop for every
+    vertex that has none, sorted by (dst, src)."""
+    n = len(rowptr) - 1
+    dst = np.repeat(np.arange(n, dtype=np.int64), np.diff(rowptr))
+    src = np.asarray(colidx, dtype=np.int64)
+    has = np.zeros(n, dtype=bool)
+    has[dst[dst == src]] = True
+    extra = np.flatnonzero(~has)
+    dst = np.concatenate([dst, extra])
+    src = np.concatenate([src, extra])
+    order = np.lexsort((src, dst))
+    return dst[order], src[order]
+
+
+def layer_forward(dst, src, n, A, W, a_src, a_dst, b, relu):
+    H = A @ W
+    s_src = H @ a_src
+    s_dst = H @ a_dst
+    x = s_src[src] + s_dst[dst]
+    e = np.where(x > 0, x, SLOPE * x)
+    m = np.full(n, -np.inf)
+    np.maximum.at(m, dst, e)
+    ex = np.exp(e - m[dst])
+    den = np.zeros(n)
+    np.add.at(den, dst, ex)
+    alpha = ex / den[dst]
+    Z = np.zeros_like(H)
+    np.add.at(Z, dst, alpha[:, None] * H[src])
+    Y = Z + (b if b is not None else 0.0)
+    out = np.maximum(Y, 0.0) if relu else Y
+    return out, dict(H=H, x=x, alpha=alpha, Z=Z)
+
+
+def layer_backward(dst, src, n, A, W, a_src, a_dst, cache, dY):
+    """Gradients of one layer given dLoss/d(Z + b) = ``dY``."""
+    H, x, alpha = cache["H"], cache["x"], cache["alpha"]
+    dH = np.zeros_like(H)
+    np.add.at(dH, src, alpha[:, None] * dY[dst])                 # through Z = sum alpha H[u]
+    dalpha = np.einsum("ij,ij->i", dY[dst], H[src])
+    t = np.zeros(n)
+    np.add.at(t, dst, alpha * dalpha)
+    de = alpha * (dalpha - t[dst])                               # softmax
+    dx = de * np.where(x > 0, 1.0, SLOPE)                        # LeakyReLU
+    ds_src = np.zeros(n)
+    ds_dst = np.zeros(n)
+    np.add.at(ds_src, src, dx)
+    np.add.at(ds_dst, dst, dx)
+    da_src = H.T @ ds_src
+    da_dst = H.T @ ds_dst
+    dH += np.outer(ds_src, a_src) + np.outer(ds_dst, a_dst)
+    return dict(gW=A.T @ dH, ga_src=da_src, ga_dst=da_dst, gb=dY.sum(axis=0), gA=dH @ W.T)
+
+
+def forward(rowptr, colidx, dims, X, weights):
+    """``weights``: per layer a dict with ``W`` [d_in, d_out], ``a_src``, ``a_dst`` [d_out] and
+    ``b`` [d_out] or None.  Returns the activations A^1..A^L and the per-layer caches."""
+    n = len(rowptr) - 1
+    dst, src = edges_with_self_loops(rowptr, colidx)
+    L = len(dims) - 1
+    A = np.asarray(X, dtype=np.float64)
+    acts, caches = [], []
+    for l in range(L):
+        w = weights[l]
+        A_in = A
+        A, cache = layer_forward(dst, src, n, A_in, np.asarray(w["W"], dtype=np.float64),
+                                 np.asarray(w["a_src"], dtype=np.float64),
+                                 np.asarray(w["a_dst"], dtype=np.float64),
+                                 None if w.get("b") is None else np.asarray(w["b"], dtype=np.float64),
+                                 relu=l < L - 1)
+        cache["A_in"] = A_in
+        acts.append(A)
+        caches.append(cache)
+    return acts, caches, (dst, src)
+
+
+def epoch(rowptr, colidx, dims, X, weights, labels, mask, relu_on=None):
+    """One full-graph epoch.  Returns ``act``, ``loss``, ``gW``, ``ga_src``, ``ga_dst``, ``gb``
+    (lists per layer) and ``gact`` (dLoss/dA^1..dLoss/dA^L)."""
+    n = len(rowptr) - 1
+    L = len(dims) - 1
+    acts, caches, (dst, src) = forward(rowptr, colidx, dims, X, weights)
+    lossv, G = fullgraph.loss(acts[-1], labels, mask)
+    out = {"act": acts, "loss": lossv, "gW": [None] * L, "ga_src": [None] * L, "ga_dst": [None] * L,
+           "gb": [None] * L, "gact": [None] * L}
+    for l in range(L - 1, -1, -1):
+        out["gact"][l] = G
+        if l < L - 1:
+            on = (acts[l] > 0) if relu_on is None or relu_on[l] is None else (np.asarray(relu_on[l]) != 0)
+            dY = G * on
+        else:
+            dY = G
+        w = weights[l]
+        g = layer_backward(dst, src, n, caches[l]["A_in"], np.asarray(w["W"], dtype=np.float64),
+                           np.asarray(w["a_src"], dtype=np.float64),
+                           np.asarray(w["a_dst"], dtype=np.float64), caches[l], dY)
+        out["gW"][l], out["ga_src"][l], out["ga_dst"][l] = g["gW"], g["ga_src"], g["ga_dst"]
+        out["gb"][l] = g["gb"] if w.get("b") is not None else None
+        G = g["gA"]
+    out["gX"] = G
+    return out

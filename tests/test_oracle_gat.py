@@ -1,0 +1,141 @@
+"""Pins for the graph-attention oracle (oracle/gat.py): the dense definition, automatic
+differentiation of that dense definition by a library (torch, fp64), finite differences, and
+the special cases in which attention reduces to a plain mean."""
+import numpy as np
+import pytest
+import torch
+
+from helpers import small_graph
+from oracle import fullgraph as og
+from oracle import gat
+
+
+def make(n, dims, seed, m_draw=None, symmetric=True):
+    rowptr, colidx = small_graph(n, m_draw or 4 * n, seed=seed, symmetric=symmetric, self_loops=False)
+    rng = np.random.default_rng(seed)
+    X = rng.standard_normal((n, dims[0]))
+    y = rng.integers(0, dims[-1], n).astype(np.int32)
+    m = (rng.random(n) < 0.6).astype(np.uint8)
+    w = []
+    for l in range(len(dims) - 1):
+        w.append({"W": rng.standard_normal((dims[l], dims[l + 1])) / np.sqrt(dims[l]),
+                  "a_src": rng.standard_normal(dims[l + 1]) * 0.7,
+                  "a_dst": rng.standard_normal(dims[l + 1]) * 0.7,
+                  "b": rng.standard_normal(dims[l + 1]) * 0.1})
+    return rowptr, colidx, X, y, m, w
+
+
+def dense_mask(rowptr, colidx):
+    n = len(rowptr) - 1
+    M = np.zeros((n, n), dtype=bool)                 # M[v, u]: u is a source of v
+    for v in range(n):
+        M[v, colidx[rowptr[v]:rowptr[v + 1]]] = True
+    M[np.arange(n), np.arange(n)] = True             # one self-loop each
+    return M
+
+
+def torch_dense_epoch(rowptr, colidx, dims, X, w, y, m):
+    """The layer definition on a dense [n, n] attention matrix, differentiated by autograd."""
+    M = torch.tensor(dense_mask(rowptr, colidx))
+    A = torch.tensor(X, dtype=torch.float64)
+    params = [{k: torch.tensor(v, dtype=torch.float64, requires_grad=True) for k, v in wl.items()}
+              for wl in w]
+    acts = []
+    L = len(dims) - 1
+    for l in range(L):
+        p = params[l]
+        H = A @ p["W"]
+        x = (H @ p["a_dst"])[:, None] + (H @ p["a_src"])[None, :]          # [v, u]
+        e = torch.nn.functional.leaky_relu(x, 0.2)
+        e = torch.where(M, e, torch.tensor(-float("inf"), dtype=torch.float64))
+        alpha = torch.softmax(e, dim=1)
+        Y = alpha @ H + p["b"]
+        A = torch.relu(Y) if l < L - 1 else Y
+        A.retain_grad()
+        acts.append(A)
+    idx = torch.tensor(np.flatnonzero(m))
+    loss = torch.nn.functional.cross_entropy(acts[-1][idx], torch.tensor(y[m != 0].astype(np.int64)))
+    loss.backward()
+    return loss.item(), acts, params
+
+
+@pytest.mark.parametrize("symmetric", [True, False])
+def test_gat_epoch_equals_dense_definition_and_autograd(symmetric):
+    n, dims = 40, (6, 7, 5, 4)
+    rowptr, colidx, X, y, m, w = make(n, dims, seed=3, symmetric=symmetric)
+    out = gat.epoch(rowptr, colidx, dims, X, w, y, m)
+    loss, acts, params = torch_dense_epoch(rowptr, colidx, dims, X, w, y, m)
+    assert abs(out["loss"] - loss) < 1e-12
+    for l in range(3):
+        assert np.abs(out["act"][l] - acts[l].detach().numpy()).max() < 1e-12
+        assert np.abs(out["gact"][l] - acts[l].grad.numpy()).max() < 1e-12
+        for ours, name in (("gW", "W"), ("ga_src", "a_src"), ("ga_dst", "a_dst"), ("gb", "b")):
+            ref = params[l][name].grad.numpy()
+            assert np.abs(out[ours][l] - ref).max() < 1e-11 * max(1.0, np.abs(ref).max()), (l, name)
+
+
+def test_gat_gradients_match_finite_differences():
+    n, dims = 25, (4, 5, 3)
+    rowptr, colidx, X, y, m, w = make(n, dims, seed=8)
+    out = gat.epoch(rowptr, colidx, dims, X, w, y, m)
+    h, worst = 1e-6, 0.0
+    for l in range(2):
+        for pname, gname in (("W", "gW"), ("a_src", "ga_src"), ("a_dst", "ga_dst"), ("b", "gb")):
+            arr, g = w[l][pname], out[gname][l]
+            for idx in np.ndindex(arr.shape):
+                old = arr[idx]
+                arr[idx] = old + h
+                lp = gat.epoch(rowptr, colidx, dims, X, w, y, m)["loss"]
+                arr[idx] = old - h
+                lm = gat.epoch(rowptr, colidx, dims, X, w, y, m)["loss"]
+                arr[idx] = old
+                worst = max(worst, abs((lp - lm) / (2 * h) - g[idx]) / np.abs(g).max())
+    assert worst < 1e-6, worst
+
+
+def test_zero_attention_vectors_give_the_mean_over_the_closed_neighbourhood():
+    n, dims = 30, (5, 6, 4)
+    rowptr, colidx, X, y, m, w = make(n, dims, seed=5)
+    for wl in w:
+        wl["a_src"][:] = 0
+        wl["a_dst"][:] = 0
+    acts, caches, (dst, src) = gat.forward(rowptr, colidx, dims, X, w)
+    M = dense_mask(rowptr, colidx).astype(np.float64)
+    S = M / M.sum(axis=1, keepdims=True)                 # row-normalised A + I
+    A = X
+    for l in range(2):
+        Y = S @ (A @ w[l]["W"]) + w[l]["b"]
+        A = np.maximum(Y, 0) if l == 0 else Y
+        assert np.abs(A - acts[l]).max() < 1e-12
+    # attention weights of a vertex sum to one, always
+    rowptr2, colidx2, X2, y2, m2, w2 = make(n, dims, seed=6)
+    _, caches, (dst, src) = gat.forward(rowptr2, colidx2, dims, X2, w2)
+    sums = np.zeros(n)
+    np.add.at(sums, dst, caches[0]["alpha"])
+    assert np.abs(sums - 1).max() < 1e-13
+
+
+def test_attention_is_invariant_to_a_shift_of_the_destination_score_sign_region():
+    # softmax over sources is unchanged when the same constant is added to every score of a
+    # destination, as long as no score crosses the LeakyReLU kink; checked per vertex on a star
+    n = 6
+    rowptr = np.array([0, 5, 5, 5, 5, 5, 5], dtype=np.int64)      # vertex 0 aggregates from 1..5
+    colidx = np.array([1, 2, 3, 4, 5], dtype=np.int32)
+    dst, src = gat.edges_with_self_loops(rowptr, colidx)
+    assert list(dst[:6]) == [0] * 6 and list(src[:6]) == [0, 1, 2, 3, 4, 5]
+    H_in = np.eye(n)
+    W = np.eye(n)
+    a_src = np.array([0.0, 1.0, 2.0, 3.0, 4.0, 5.0])
+    a_dst = np.zeros(n)
+    out, cache = gat.layer_forward(dst, src, n, H_in, W, a_src, a_dst, None, relu=False)
+    want = np.exp(a_src) / np.exp(a_src).sum()                     # all scores >= 0: identity branch
+    assert np.abs(cache["alpha"][:6] - want).max() < 1e-14
+    assert np.abs(out[0] - want).max() < 1e-14                     # Z[0] = sum alpha_u e_u
+    a_dst2 = np.zeros(n)
+    a_dst2[0] = 10.0                                               # shifts every score of vertex 0
+    _, cache2 = gat.layer_forward(dst, src, n, H_in, W, a_src, a_dst2, None, relu=False)
+    assert np.abs(cache2["alpha"][:6] - want).max() < 1e-14
+    # negative scores go through the 0.2 slope
+    _, cache3 = gat.layer_forward(dst, src, n, H_in, W, -a_src, a_dst, None, relu=False)
+    want3 = np.exp(-0.2 * a_src) / np.exp(-0.2 * a_src).sum()
+    assert np.abs(cache3["alpha"][:6] - want3).max() < 1e-14
