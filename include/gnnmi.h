@@ -47,7 +47,12 @@ typedef enum {
     GNN_EUNSUPPORTED = 5  /* valid request this build does not implement */
 } gnn_status;
 
-typedef enum { GNN_GCN = 0, GNN_SAGE_MEAN = 1 } gnn_model;
+/* GNN_GAT: graph-attention layers with one head (Velickovic et al.; the second model family of
+ * the paper's evaluation): H = A^{l-1} W, e(u->v) = LeakyReLU_0.2(a_src.H[u] + a_dst.H[v]) over
+ * the sources of v and v itself, softmax over the sources, A^l = act(sum alpha H[u] + b).
+ * weights[3(l-1)+1] holds the two attention vectors as [2, d_l] (a_src, then a_dst), fp32.
+ * GNN_F32 and the resident schedule only. */
+typedef enum { GNN_GCN = 0, GNN_SAGE_MEAN = 1, GNN_GAT = 2 } gnn_model;
 typedef enum { GNN_F32 = 0, GNN_BF16 = 1 } gnn_dtype; /* storage type of activations/weights */
 typedef enum {
     GNN_PART_USER = 0,
@@ -267,6 +272,11 @@ gnn_status gnn_layer_is_transform_first(const gnn_ctx *ctx, int32_t layer, int32
  *             grad A^{l-1}_own += dY_p W_s^T, grad H [R_p] += S_p^T dY_p), then
  *             gnn_layer_transform_bwd(layer, p) for every p (grad W += A_p^{l-1 T} grad H_p,
  *             grad A^{l-1}_own += grad H_p W^T) before layer-1 starts.
+ * One scratch buffer holds H for the layer being worked on: starting the transform sweep of
+ * another layer invalidates it.  Graph-attention layers (GNN_GAT) always transform first and
+ * their backward pass needs H, the scores and the gathered rows again: for such a layer call
+ * gnn_layer_transform_fwd for every p once more before its backward sweep (unless H still
+ * holds this layer), and gnn_gather_boundary(layer, p) before each gnn_layer_bwd(layer, p).
  * GNN_ESTATE when the layer aggregates first or a sweep is incomplete. */
 gnn_status gnn_layer_transform_fwd(gnn_ctx *ctx, int32_t layer, int32_t p, void *stream);
 gnn_status gnn_layer_transform_bwd(gnn_ctx *ctx, int32_t layer, int32_t p, void *stream);

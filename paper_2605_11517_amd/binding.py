@@ -11,7 +11,7 @@ import os
 
 import numpy as np
 
-GNN_GCN, GNN_SAGE_MEAN = 0, 1
+GNN_GCN, GNN_SAGE_MEAN, GNN_GAT = 0, 1, 2
 GNN_F32, GNN_BF16 = 0, 1
 GNN_PART_USER, GNN_PART_RANDOM, GNN_PART_LP, GNN_PART_SWITCHING = 0, 1, 2, 3
 GNN_PART_SWITCHING_DEVICE = 4
@@ -19,7 +19,7 @@ KERNEL_CLASSES = ("gather", "spmm", "gemm_fwd", "loss", "act_bwd", "gemm_dw", "g
                   "spmm_t", "scatter", "other", "spmm_reduce")
 STATUS = {0: "GNN_OK", 1: "GNN_EINVAL", 2: "GNN_ENOMEM", 3: "GNN_EHIP", 4: "GNN_ESTATE",
           5: "GNN_EUNSUPPORTED"}
-_MODEL = {"gcn": GNN_GCN, "sage": GNN_SAGE_MEAN}
+_MODEL = {"gcn": GNN_GCN, "sage": GNN_SAGE_MEAN, "gat": GNN_GAT}
 _PART = {"user": GNN_PART_USER, "random": GNN_PART_RANDOM, "lp": GNN_PART_LP,
          "switching": GNN_PART_SWITCHING, "switching_device": GNN_PART_SWITCHING_DEVICE}
 
@@ -342,7 +342,10 @@ class Session:
         for l in range(self.L):
             for key in ("W", "Ws", "b"):
                 a = weights[l].get(key)
-                use = a is not None and (key != "Ws" or self.model == GNN_SAGE_MEAN) \
+                if key == "Ws" and self.model == GNN_GAT:
+                    # graph attention: the second slot holds the two attention vectors [2, d_out]
+                    a = np.stack([weights[l]["a_src"], weights[l]["a_dst"]])
+                use = a is not None and (key != "Ws" or self.model in (GNN_SAGE_MEAN, GNN_GAT)) \
                     and (key != "b" or has_bias)
                 if use:
                     wt = t.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(self.dev)

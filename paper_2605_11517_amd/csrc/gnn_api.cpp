@@ -35,6 +35,7 @@ void free_device(DevMeta& D)
     if (D.tcol) (void)hipFree(D.tcol);
     if (D.tw) (void)hipFree(D.tw);
     if (D.order) (void)hipFree(D.order);
+    if (D.tperm) (void)hipFree(D.tperm);
     for (DevMeta::Plan* P : {&D.fwd, &D.bwd}) {
         if (P->range_rows) (void)hipFree(P->range_rows);
         if (P->seg_row) (void)hipFree(P->seg_row);
@@ -75,6 +76,7 @@ gnn_status ensure_device(gnn_ctx* c)
     step(upload(D.tcol, M.tcol));
     step(upload(D.tw, M.tw));
     step(upload(D.order, M.order));
+    step(upload(D.tperm, M.tperm));
     for (int dir = 0; dir < 2; ++dir) {
         const HostMeta::Plan& H = dir == 0 ? M.plan_fwd : M.plan_bwd;
         DevMeta::Plan& P = dir == 0 ? D.fwd : D.bwd;
@@ -111,6 +113,11 @@ void compute_workspace(gnn_ctx* c)
         int sp = gemm_tn_splits(max_np, c->dims[(size_t)l], c->dims[(size_t)l + 1]);
         part = std::max(part, (int64_t)sp * c->dims[(size_t)l] * c->dims[(size_t)l + 1]);
     }
+    // rows that pass through staging, Z, the padded dY copy and the segment partial sums are as
+    // wide as the widest aggregated row: an input width, or the padded output width of a layer
+    // that transforms first
+    for (int32_t l = 1; l <= L; ++l)
+        if (c->transform_first(l)) din = std::max<int64_t>(din, c->padded(l));
     Workspace& w = c->ws;
     w.staging_bytes = align_up(std::max<int64_t>(1, max_b * din * 4));
     int64_t o = 0;
@@ -120,7 +127,8 @@ void compute_workspace(gnn_ctx* c)
     w.dz = take(max_np * din);
     w.dga = take(max_r * din);
     w.partial = take(part);
-    w.colpart = take(act_bwd_partial_floats(max_np, (int32_t)dout));
+    w.colpart = take(std::max(act_bwd_partial_floats(max_np, (int32_t)dout),
+                              gat_rank1_partial_floats(max_np, (int32_t)dout)));
     w.losspart = take(loss_partial_floats(M.n, M.k));
     w.scalars = take(64);
     w.segpart = take(std::max(M.plan_fwd.max_segs, M.plan_bwd.max_segs) * din);
@@ -131,6 +139,16 @@ void compute_workspace(gnn_ctx* c)
     if (hp > 0) {
         w.h = take(M.n * hp);
         w.gh = take(M.n * hp);
+    }
+    if (c->model == GNN_GAT) {
+        w.ssrc = take(M.n);
+        w.sdst = take(M.n);
+        w.gssrc = take(M.n);
+        w.gsdst = take(M.n);
+        w.bs = take(max_b);
+        w.att = take(M.stats.max_nnz);
+        w.dal = take(M.stats.max_nnz);
+        w.twatt = take(M.stats.max_nnz);
     }
     w.scratch_bytes = o;
 }
@@ -147,25 +165,6 @@ gnn_status check_lp(gnn_ctx* c, int32_t layer, int32_t p)
     return GNN_OK;
 }
 
-SpmmItems plan_items(const HostMeta::Plan& H, const DevMeta::Plan& P, int32_t p)
-{
-    SpmmItems it;
-    const int64_t r0 = H.range_off[(size_t)p], s0 = H.seg_off[(size_t)p], l0 = H.long_off[(size_t)p];
-    it.nranges = H.range_off[(size_t)p + 1] - r0 - 1;
-    if (it.nranges < 0) it.nranges = 0;
-    it.range_rows = P.range_rows ? P.range_rows + r0 : nullptr;
-    it.nsegs = H.seg_off[(size_t)p + 1] - s0;
-    it.seg_row = P.seg_row ? P.seg_row + s0 : nullptr;
-    it.seg_begin = P.seg_begin ? P.seg_begin + s0 : nullptr;
-    it.seg_len = P.seg_len ? P.seg_len + s0 : nullptr;
-    it.nlong = H.long_off[(size_t)p + 1] - l0;
-    it.long_row = P.long_row ? P.long_row + l0 : nullptr;
-    it.long_first = P.long_first ? P.long_first + l0 : nullptr;
-    it.long_nseg = P.long_nseg ? P.long_nseg + l0 : nullptr;
-    it.nshort = H.rows_off[(size_t)p + 1] - H.rows_off[(size_t)p];
-    it.rows_sorted = P.rows_sorted ? P.rows_sorted + H.rows_off[(size_t)p] : nullptr;
-    return it;
-}
 
 // Z_p = S_p [in_own ; staging]
 void run_spmm_fwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, hipStream_t s)
@@ -193,6 +192,26 @@ void run_spmm_fwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, hipS
 
 namespace gnnmi {
 
+SpmmItems plan_items(const HostMeta::Plan& H, const DevMeta::Plan& P, int32_t p)
+{
+    SpmmItems it;
+    const int64_t r0 = H.range_off[(size_t)p], s0 = H.seg_off[(size_t)p], l0 = H.long_off[(size_t)p];
+    it.nranges = H.range_off[(size_t)p + 1] - r0 - 1;
+    if (it.nranges < 0) it.nranges = 0;
+    it.range_rows = P.range_rows ? P.range_rows + r0 : nullptr;
+    it.nsegs = H.seg_off[(size_t)p + 1] - s0;
+    it.seg_row = P.seg_row ? P.seg_row + s0 : nullptr;
+    it.seg_begin = P.seg_begin ? P.seg_begin + s0 : nullptr;
+    it.seg_len = P.seg_len ? P.seg_len + s0 : nullptr;
+    it.nlong = H.long_off[(size_t)p + 1] - l0;
+    it.long_row = P.long_row ? P.long_row + l0 : nullptr;
+    it.long_first = P.long_first ? P.long_first + l0 : nullptr;
+    it.long_nseg = P.long_nseg ? P.long_nseg + l0 : nullptr;
+    it.nshort = H.rows_off[(size_t)p + 1] - H.rows_off[(size_t)p];
+    it.rows_sorted = P.rows_sorted ? P.rows_sorted + H.rows_off[(size_t)p] : nullptr;
+    return it;
+}
+
 void collect_profile(gnn_ctx* c)
 {
     for (int i = 0; i < GNN_K_COUNT; ++i) { c->prof_ms[i] = 0; c->prof_launches[i] = 0; }
@@ -215,6 +234,7 @@ void zero_weight_grads(gnn_ctx* c, hipStream_t s)
         const int64_t wsz = (int64_t)c->dims[(size_t)l] * c->dims[(size_t)l + 1] * 4;
         launch_fill_zero(c->gw[(size_t)3 * l], wsz, s);
         if (c->model == GNN_SAGE_MEAN) launch_fill_zero(c->gw[(size_t)3 * l + 1], wsz, s);
+        if (c->model == GNN_GAT) launch_fill_zero(c->gw[(size_t)3 * l + 1], (int64_t)2 * c->dims[(size_t)l + 1] * 4, s);
         if (c->has_bias) launch_fill_zero(c->gw[(size_t)3 * l + 2], (int64_t)c->dims[(size_t)l + 1] * 4, s);
     }
 }
@@ -487,7 +507,10 @@ gnn_status gnn_create(const gnn_config* cfg, gnn_ctx** out)
     auto bad = [&](gnn_status st, const char* m) { g_create_error = m; return st; };
     if (!cfg || !out) return bad(GNN_EINVAL, "cfg and out must be non-null");
     *out = nullptr;
-    if (cfg->model != GNN_GCN && cfg->model != GNN_SAGE_MEAN) return bad(GNN_EINVAL, "unknown model");
+    if (cfg->model != GNN_GCN && cfg->model != GNN_SAGE_MEAN && cfg->model != GNN_GAT)
+        return bad(GNN_EINVAL, "unknown model");
+    if (cfg->model == GNN_GAT && (cfg->dtype != GNN_F32 || cfg->hbm_budget_bytes != 0))
+        return bad(GNN_EUNSUPPORTED, "graph-attention layers are built for GNN_F32 and the resident schedule");
     if (cfg->dtype != GNN_F32 && cfg->dtype != GNN_BF16) return bad(GNN_EINVAL, "unknown dtype");
     if (cfg->n_layers < 1 || cfg->n_layers > 64) return bad(GNN_EINVAL, "n_layers must be in 1..64");
     if (!cfg->dims) return bad(GNN_EINVAL, "dims is null");
@@ -627,8 +650,8 @@ gnn_status gnn_bind(gnn_ctx* c, const void* feat, void* const* act, void* const*
     for (int32_t l = 0; l < L; ++l) {
         if (!act[l] || !grad_act[l]) return c->fail(GNN_EINVAL, "null activation or gradient buffer");
         if (!weights[3 * l] || !grad_w[3 * l]) return c->fail(GNN_EINVAL, "null weight or weight-gradient buffer");
-        if (c->model == GNN_SAGE_MEAN && (!weights[3 * l + 1] || !grad_w[3 * l + 1]))
-            return c->fail(GNN_EINVAL, "null self-weight buffer for a SAGE layer");
+        if ((c->model == GNN_SAGE_MEAN || c->model == GNN_GAT) && (!weights[3 * l + 1] || !grad_w[3 * l + 1]))
+            return c->fail(GNN_EINVAL, "null self-weight (SAGE) or attention-vector (GAT) buffer");
         if (c->has_bias && (!weights[3 * l + 2] || !grad_w[3 * l + 2]))
             return c->fail(GNN_EINVAL, "null bias buffer although has_bias is set");
     }
@@ -660,6 +683,7 @@ gnn_status gnn_bind(gnn_ctx* c, const void* feat, void* const* act, void* const*
     std::fill(c->xf_fwd_done.begin(), c->xf_fwd_done.end(), 0);
     std::fill(c->xf_bwd_done.begin(), c->xf_bwd_done.end(), 0);
     std::fill(c->bwd_done.begin(), c->bwd_done.end(), 0);
+    c->h_layer = 0;
     if (c->streaming()) {
         st = stream_engine_create(c);
         if (st != GNN_OK) return st;
@@ -694,6 +718,12 @@ gnn_status gnn_gather_boundary(gnn_ctx* c, int32_t layer, int32_t p, void* strea
         // the layer aggregates H = A^{l-1} W: every partition's rows of H must exist
         if (all_done(c->xf_fwd_done, layer, M.k) < M.k)
             return c->fail(GNN_ESTATE, "transform-first layer: gnn_layer_transform_fwd has not covered every partition");
+        if (c->model == GNN_GAT) {
+            gat_gather(c, layer, p, s);
+            c->staged_layer = layer;
+            c->staged_p = p;
+            return check_launch(c, "gnn_gather_boundary");
+        }
         Timed t(c, s, GNN_K_GATHER);
         launch_gather_rows(c->scratch + c->ws.h, c->D.bnd + b0, c->staging, nb, (int64_t)c->padded(layer) * 4, s);
     } else {
@@ -716,7 +746,9 @@ gnn_status gnn_layer_fwd(gnn_ctx* c, int32_t layer, int32_t p, void* stream)
     hipStream_t s = (hipStream_t)stream;
     const int64_t r0 = c->M.off[(size_t)p];
     const int32_t dout = c->dims[(size_t)layer];
-    if (c->transform_first(layer))
+    if (c->model == GNN_GAT)
+        gat_layer_fwd(c, layer, p, s);
+    else if (c->transform_first(layer))
         xf_aggregate_fwd(c, layer, p, s);
     else
         compute_fwd(c, layer, p, c->layer_input(layer, r0),
@@ -752,6 +784,16 @@ gnn_status gnn_layer_transform_fwd(gnn_ctx* c, int32_t layer, int32_t p, void* s
     if (!c->transform_first(layer)) return c->fail(GNN_ESTATE, "this layer aggregates first");
     hipStream_t s = (hipStream_t)stream;
     const HostMeta& M = c->M;
+    if (c->h_layer != layer) {
+        // one buffer holds H for whichever layer is being worked on
+        std::fill(c->xf_fwd_done.begin(), c->xf_fwd_done.end(), 0);
+        c->h_layer = layer;
+    }
+    if (c->model == GNN_GAT) {
+        gat_transform_fwd(c, layer, p, s);
+        c->xf_fwd_done[(size_t)(layer - 1) * (size_t)M.k + (size_t)p] = 1;
+        return check_launch(c, "gnn_layer_transform_fwd");
+    }
     const int64_t r0 = M.off[(size_t)p], np = M.off[(size_t)p + 1] - r0;
     const int32_t din = c->dims[(size_t)layer - 1], dout = c->dims[(size_t)layer], dp = c->padded(layer);
     float* H = (float*)(c->scratch + c->ws.h) + r0 * dp;
@@ -781,6 +823,11 @@ gnn_status gnn_layer_transform_bwd(gnn_ctx* c, int32_t layer, int32_t p, void* s
         return c->fail(GNN_ESTATE, "gnn_layer_bwd of this layer has not covered every partition");
     hipStream_t s = (hipStream_t)stream;
     const HostMeta& M = c->M;
+    if (c->model == GNN_GAT) {
+        gat_transform_bwd(c, layer, p, s);
+        c->xf_bwd_done[(size_t)(layer - 1) * (size_t)M.k + (size_t)p] = 1;
+        return check_launch(c, "gnn_layer_transform_bwd");
+    }
     const int64_t r0 = M.off[(size_t)p], np = M.off[(size_t)p + 1] - r0;
     const int32_t din = c->dims[(size_t)layer - 1], dout = c->dims[(size_t)layer], dp = c->padded(layer);
     const float* gH = (const float*)(c->scratch + c->ws.gh) + r0 * dp;
@@ -844,6 +891,18 @@ gnn_status gnn_layer_bwd(gnn_ctx* c, int32_t layer, int32_t p, void* stream)
     if (layer < c->L && c->transform_first(layer + 1) && all_done(c->xf_bwd_done, layer + 1, c->M.k) < c->M.k)
         return c->fail(GNN_ESTATE, "gnn_layer_transform_bwd of layer+1 has not covered every partition");
     hipStream_t s = (hipStream_t)stream;
+    if (c->model == GNN_GAT) {
+        // attention needs the gathered rows of H again (regather), and recomputes its weights
+        if (c->staged_layer != layer || c->staged_p != p)
+            return c->fail(GNN_ESTATE, "staging does not hold this (layer, partition); call gnn_gather_boundary first");
+        if (c->bwd_done[(size_t)layer] == 0) {
+            gat_bwd_begin(c, layer, s);
+            for (int32_t q = 0; q < c->M.k; ++q) c->xf_bwd_done[(size_t)(layer - 1) * (size_t)c->M.k + (size_t)q] = 0;
+        }
+        gat_layer_bwd(c, layer, p, s);
+        c->bwd_done[(size_t)layer] += 1;
+        return check_launch(c, "gnn_layer_bwd");
+    }
     if (c->transform_first(layer)) {
         // no regather and no recompute: the layer aggregated H, whose gradient is accumulated here
         if (c->bwd_done[(size_t)layer] == 0) {
@@ -918,9 +977,14 @@ gnn_status gnn_epoch(gnn_ctx* c, void* stream, float* loss_out)
     if ((st = gnn_loss(c, stream)) != GNN_OK) return st;
     for (int32_t l = L; l >= 1; --l) {
         const bool xf = c->transform_first(l);
+        const bool regather = !xf || c->model == GNN_GAT;
+        if (c->model == GNN_GAT && c->h_layer != l)
+            // attention needs H and the scores of this layer again: recompute them
+            for (int32_t t = 0; t < k; ++t)
+                if ((st = gnn_layer_transform_fwd(c, l, c->M.sched[(size_t)t], stream)) != GNN_OK) return st;
         for (int32_t t = 0; t < k; ++t) {
             const int32_t p = c->M.sched[(size_t)t];
-            if (!xf && (st = gnn_gather_boundary(c, l, p, stream)) != GNN_OK) return st;
+            if (regather && (st = gnn_gather_boundary(c, l, p, stream)) != GNN_OK) return st;
             if ((st = gnn_layer_bwd(c, l, p, stream)) != GNN_OK) return st;
         }
         if (xf)
@@ -950,7 +1014,7 @@ gnn_status gnn_bind_optimizer(gnn_ctx* c, void* const* m, void* const* v)
     c->opt_v.assign((size_t)3 * L, nullptr);
     for (int32_t l = 0; l < L; ++l)
         for (int j = 0; j < 3; ++j) {
-            const bool needed = j == 0 || (j == 1 && c->model == GNN_SAGE_MEAN) || (j == 2 && c->has_bias);
+            const bool needed = j == 0 || (j == 1 && c->model != GNN_GCN) || (j == 2 && c->has_bias);
             if (needed && (!m[3 * l + j] || !v[3 * l + j])) {
                 c->opt_m.clear();
                 c->opt_v.clear();
@@ -980,10 +1044,11 @@ gnn_status gnn_optimizer_step(gnn_ctx* c, const gnn_optimizer* opt, int64_t step
             float* w = (float*)const_cast<char*>(c->w[(size_t)(3 * l + j)]);
             float* g = c->gw[(size_t)(3 * l + j)];
             if (!w || !g) continue;
-            if (j == 1 && c->model != GNN_SAGE_MEAN) continue;
+            if (j == 1 && c->model == GNN_GCN) continue;
             if (j == 2 && !c->has_bias) continue;
-            const int64_t cnt = j == 2 ? (int64_t)c->dims[(size_t)l + 1]
-                                       : (int64_t)c->dims[(size_t)l] * c->dims[(size_t)l + 1];
+            int64_t cnt = j == 2 ? (int64_t)c->dims[(size_t)l + 1]
+                                 : (int64_t)c->dims[(size_t)l] * c->dims[(size_t)l + 1];
+            if (j == 1 && c->model == GNN_GAT) cnt = (int64_t)2 * c->dims[(size_t)l + 1];
             if (opt->kind == GNN_OPT_ADAM)
                 launch_adam(w, g, c->opt_m[(size_t)(3 * l + j)], c->opt_v[(size_t)(3 * l + j)], cnt, opt->lr,
                             opt->beta1, opt->beta2, opt->eps, opt->weight_decay, corr1, corr2, s);

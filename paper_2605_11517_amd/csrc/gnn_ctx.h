@@ -21,6 +21,7 @@ struct DevMeta {
     int32_t* tcol = nullptr;
     float* tw = nullptr;
     int32_t* order = nullptr;
+    int32_t* tperm = nullptr;
     struct Plan {
         int32_t* range_rows = nullptr;
         int32_t* seg_row = nullptr;
@@ -38,6 +39,9 @@ struct Workspace {  // byte offsets into `scratch`
     int64_t z = 0, dy = 0, dz = 0, dga = 0, partial = 0, colpart = 0, losspart = 0, scalars = 0,
             segpart = 0;
     int64_t h = 0, gh = 0;     // transform-first layers: H = A W and its gradient, n x padded width
+    // graph attention: per-vertex scores and their gradients, staged boundary scores, per-entry
+    // attention weights, edge-wise products, attention weights in transposed order
+    int64_t ssrc = 0, sdst = 0, gssrc = 0, gsdst = 0, bs = 0, att = 0, dal = 0, twatt = 0;
     int64_t staging_bytes = 0, scratch_bytes = 0;
 };
 
@@ -74,12 +78,14 @@ struct gnn_ctx {
     int32_t order_mode = 0;
     bool transform_first(int32_t layer) const
     {
+        if (model == GNN_GAT) return true;       // attention scores are taken from H = A W
         return order_mode == 1 && !streaming() && !bf16() &&
                dims[(size_t)layer] < dims[(size_t)layer - 1];
     }
     // width of H rows: d_layer rounded up to whole 16-byte vectors
     int32_t padded(int32_t layer) const { return (dims[(size_t)layer] + 3) / 4 * 4; }
     std::vector<uint8_t> xf_fwd_done, xf_bwd_done;   // L * k: transform sweeps of such layers
+    int32_t h_layer = 0;                             // layer whose H = A W the scratch buffer holds
     // schedule state
     int32_t staged_layer = -1, staged_p = -1;
     std::vector<uint8_t> fwd_done;      // L * k
@@ -169,6 +175,15 @@ void compute_bwd_self(gnn_ctx* c, int32_t layer, int32_t p, const char* dY, floa
                       hipStream_t s);
 
 void zero_weight_grads(gnn_ctx* c, hipStream_t s);
+SpmmItems plan_items(const HostMeta::Plan& H, const DevMeta::Plan& P, int32_t p);
+
+// gat.cpp: the steps of a graph-attention layer for one partition
+void gat_transform_fwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s);
+void gat_gather(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s);
+void gat_layer_fwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s);
+void gat_bwd_begin(gnn_ctx* c, int32_t layer, hipStream_t s);
+void gat_layer_bwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s);
+void gat_transform_bwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s);
 void collect_profile(gnn_ctx* c);
 
 // streaming.cpp

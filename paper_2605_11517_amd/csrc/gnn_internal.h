@@ -38,7 +38,9 @@ struct HostMeta {
     std::vector<int64_t> toff;      // k+1, offset of partition p's rows in trp
     std::vector<int64_t> trp;       // sum |R_p| + 1, positions into tcol / tw
     std::vector<int32_t> tcol;      // local destination row (0 .. n_p)
-    std::vector<float> tw;          // weight of the entry (both models)
+    std::vector<float> tw;          // weight of the entry (GCN, SAGE)
+    std::vector<int32_t> tperm;     // GAT: position of the entry in the forward operator, minus the
+                                    // partition's first position
     std::vector<int32_t> sched;     // k: order in which an epoch walks the partitions
     gnn_stats stats{};
     int32_t part_iterations = 0;          // switching-aware partitioner: iterations run
@@ -199,6 +201,42 @@ void launch_loss_finish(const float* partial, int64_t nparts, const unsigned lon
                         float* loss_dev, hipStream_t s);
 
 void launch_fill_zero(void* p, int64_t bytes, hipStream_t s);
+
+// ---- graph attention (kernels_gat.hip) ----------------------------------------------------
+// Rows of one partition for the row-wise attention passes: rp points at the partition's first
+// row pointer, col / att / dal are indexed with absolute positions (minus e0 for the
+// per-partition arrays), s_src of a local column c is ssrc_own[c] or ssrc_bnd[c - n_own].
+struct GatRowsHost {
+    const int64_t* rp = nullptr;
+    const int32_t* col = nullptr;
+    int64_t e0 = 0, n_own = 0;
+    const float* ssrc_own = nullptr;
+    const float* ssrc_bnd = nullptr;
+    const float* sdst_own = nullptr;
+    SpmmItems items;
+};
+void launch_gat_scores(const float* H, int32_t ld, int32_t f, int64_t rows, const float* a_src,
+                       const float* a_dst, float* ssrc, float* sdst, hipStream_t s);
+// att[e - e0] = softmax over each row of LeakyReLU_0.2(s_src(col e) + s_dst(row))
+void launch_gat_attention(const GatRowsHost& h, float* att, hipStream_t s);
+// dal[e - e0] = dy[row,:] . src(col e)[:]  (rows of width ld, a multiple of 4)
+void launch_gat_dots(const int64_t* rp, const int32_t* col, int64_t e0, int64_t n_own, const float* a_rows,
+                     const float* b_rows, const float* dy, int32_t ld, float* dal, const SpmmItems& items,
+                     hipStream_t s);
+// dal <- gradient of the pre-activation scores (through softmax and LeakyReLU); gs_dst_own[row] = row sum
+void launch_gat_bwd_scalars(const GatRowsHost& h, const float* att, float* dal, float* gs_dst_own, hipStream_t s);
+// transposed rows: tw_att[pos - e0] = att[tperm[pos]]; with dpre != null also
+// gs_src[owner row of transposed row i] += sum over the row of dpre[tperm[pos]]
+void launch_gat_transposed(const int64_t* trp, const int32_t* tperm, int64_t e0, int64_t n_own,
+                           int64_t base_row, const int32_t* bnd, const SpmmItems& items, const float* att,
+                           const float* dpre, float* tw_att, float* gs_src, hipStream_t s);
+// gH += gs_src a_src^T + gs_dst a_dst^T over `rows` rows; partial column sums of gs_src H and
+// gs_dst H (2 f floats per block of 256 rows) for the gradients of the attention vectors
+int64_t gat_rank1_partial_floats(int64_t rows, int32_t f);
+void launch_gat_rank1(float* gH, const float* H, int32_t ld, int32_t f, int64_t rows, const float* gs_src,
+                      const float* gs_dst, const float* a_src, const float* a_dst, float* partial, hipStream_t s);
+// out[c] += sum over b < nblocks of partial[b * d + c]
+void launch_colsum_finish(const float* partial, int64_t nblocks, int32_t d, float* out, hipStream_t s);
 
 // Transform-first layers: out = (accumulate ? out : 0) + z[:, :d] (+ bias), optional relu, with
 // z's row stride ldz >= d; and a row copy into a wider, zero-padded row.

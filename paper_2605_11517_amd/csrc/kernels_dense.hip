@@ -442,6 +442,13 @@ void launch_dropout(void* a, int is_bf16, const int32_t* orig_of_row, int64_t ro
                            orig_of_row, rows, d, (unsigned long long)key, threshold, scale);
 }
 
+void launch_colsum_finish(const float* partial, int64_t nblocks, int32_t d, float* out, hipStream_t s)
+{
+    if (nblocks <= 0 || d <= 0) return;
+    hipLaunchKernelGGL(k_colsum_finish, dim3((unsigned)((d + 31) / 32)), dim3(kBlock), 0, s, partial, nblocks,
+                       d, out);
+}
+
 void launch_add_padded(float* out, const float* z, int64_t rows, int32_t d, int32_t ldz,
                        const float* bias, int accumulate, int relu, hipStream_t s)
 {

@@ -1,0 +1,416 @@
+// Kernels of the graph-attention layers (one head, LeakyReLU slope 0.2; Velickovic et al.,
+// the model family the paper evaluates next to GCN and GraphSAGE).  A layer transforms first:
+// H = A^{l-1} W, s_src = H a_src, s_dst = H a_dst per vertex; a partition then gathers the rows
+// of H and the scores s_src of its boundary vertices, computes the attention weight of every
+// entry of T_p and aggregates with them (the aggregation kernel of the other models, with the
+// attention weights as entry weights).  The backward pass regathers, recomputes the attention
+// weights and needs one more edge-wise kernel: the dot product dY[v] . H[u] per entry.
+//
+// Row-wise scalar passes come in two shapes: a wavefront walks the short rows of a range item
+// one after the other; a whole workgroup cooperates on one long row.  All reductions are
+// shuffles and fixed-order LDS sums, so results are reproducible.
+#include "gnn_internal.h"
+
+namespace gnnmi {
+namespace {
+
+constexpr int kWave = 64;
+constexpr int kBlock = 256;
+constexpr float kSlope = 0.2f;
+
+__device__ inline float wave_sum(float v)
+{
+#pragma unroll
+    for (int m = 1; m < kWave; m <<= 1) v += __shfl_xor(v, m, kWave);
+    return v;
+}
+__device__ inline float wave_max(float v)
+{
+#pragma unroll
+    for (int m = 1; m < kWave; m <<= 1) v = fmaxf(v, __shfl_xor(v, m, kWave));
+    return v;
+}
+// BLOCK: every thread of the workgroup calls these the same number of times
+template <bool BLOCK> __device__ inline float red_sum(float v, float* sm)
+{
+    v = wave_sum(v);
+    if (!BLOCK) return v;
+    __syncthreads();
+    if (threadIdx.x % kWave == 0) sm[threadIdx.x / kWave] = v;
+    __syncthreads();
+    return (sm[0] + sm[1]) + (sm[2] + sm[3]);
+}
+template <bool BLOCK> __device__ inline float red_max(float v, float* sm)
+{
+    v = wave_max(v);
+    if (!BLOCK) return v;
+    __syncthreads();
+    if (threadIdx.x % kWave == 0) sm[threadIdx.x / kWave] = v;
+    __syncthreads();
+    return fmaxf(fmaxf(sm[0], sm[1]), fmaxf(sm[2], sm[3]));
+}
+
+struct GatRows {
+    const int64_t* rp;          // row pointers of the partition's rows (absolute positions)
+    const int32_t* col;         // local columns (absolute positions)
+    int64_t e0;                 // first absolute position of the partition
+    int64_t n_own;
+    const float* ssrc_own;      // s_src of the partition's own rows
+    const float* ssrc_bnd;      // s_src of its boundary rows (staged)
+    const float* sdst_own;
+    // work decomposition
+    const int32_t* range_rows;
+    int64_t nranges;
+    const int32_t* long_row;
+    int64_t nlong;
+    __device__ float ssrc(int32_t c) const { return c < n_own ? ssrc_own[c] : ssrc_bnd[c - n_own]; }
+};
+
+__device__ inline float lrelu(float x) { return x > 0.f ? x : kSlope * x; }
+
+// s_src[r] = H[r,:] . a_src, s_dst[r] = H[r,:] . a_dst; one wavefront per row
+__global__ __launch_bounds__(kBlock) void k_gat_scores(const float* __restrict__ H, int32_t ld, int32_t f,
+                                                       int64_t rows, const float* __restrict__ a_src,
+                                                       const float* __restrict__ a_dst,
+                                                       float* __restrict__ ssrc, float* __restrict__ sdst)
+{
+    const int lane = threadIdx.x % kWave;
+    const int64_t r = (int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;
+    if (r >= rows) return;
+    float s1 = 0.f, s2 = 0.f;
+    for (int j = lane; j < f; j += kWave) {
+        const float h = H[r * ld + j];
+        s1 += h * a_src[j];
+        s2 += h * a_dst[j];
+    }
+    s1 = wave_sum(s1);
+    s2 = wave_sum(s2);
+    if (lane == 0) {
+        ssrc[r] = s1;
+        sdst[r] = s2;
+    }
+}
+
+// attention weights of one row: att[e - e0] = softmax over the row's entries of
+// LeakyReLU(s_src(col) + s_dst(row))
+template <bool BLOCK>
+__device__ inline void att_row(const GatRows& g, int32_t row, float* __restrict__ att, float* sm)
+{
+    constexpr int T = BLOCK ? kBlock : kWave;
+    const int t = BLOCK ? threadIdx.x : threadIdx.x % kWave;
+    const int64_t eb = g.rp[row], ee = g.rp[row + 1];
+    const float sd = g.sdst_own[row];
+    float m = -INFINITY;
+    for (int64_t e = eb + t; e < ee; e += T) m = fmaxf(m, lrelu(g.ssrc(g.col[e]) + sd));
+    m = red_max<BLOCK>(m, sm);
+    float s = 0.f;
+    for (int64_t e = eb + t; e < ee; e += T) s += expf(lrelu(g.ssrc(g.col[e]) + sd) - m);
+    s = red_sum<BLOCK>(s, sm);
+    const float inv = 1.f / s;
+    for (int64_t e = eb + t; e < ee; e += T) att[e - g.e0] = expf(lrelu(g.ssrc(g.col[e]) + sd) - m) * inv;
+}
+
+// after the edge-wise dot products dal[e] = dY[row] . H[col]: t = sum att dal;
+// dal[e] <- att (dal - t) LeakyReLU'(x)  (gradient of the pre-activation score);
+// gs_dst[row] = sum of those
+template <bool BLOCK>
+__device__ inline void bwd_row(const GatRows& g, int32_t row, const float* __restrict__ att,
+                               float* __restrict__ dal, float* __restrict__ gs_dst_own, float* sm)
+{
+    constexpr int T = BLOCK ? kBlock : kWave;
+    const int t = BLOCK ? threadIdx.x : threadIdx.x % kWave;
+    const int64_t eb = g.rp[row], ee = g.rp[row + 1];
+    const float sd = g.sdst_own[row];
+    float tv = 0.f;
+    for (int64_t e = eb + t; e < ee; e += T) tv += att[e - g.e0] * dal[e - g.e0];
+    tv = red_sum<BLOCK>(tv, sm);
+    float ds = 0.f;
+    for (int64_t e = eb + t; e < ee; e += T) {
+        const float x = g.ssrc(g.col[e]) + sd;
+        const float dp = att[e - g.e0] * (dal[e - g.e0] - tv) * (x > 0.f ? 1.f : kSlope);
+        dal[e - g.e0] = dp;
+        ds += dp;
+    }
+    ds = red_sum<BLOCK>(ds, sm);
+    if (t == 0) gs_dst_own[row] = ds;
+}
+
+// MODE 0: attention weights; MODE 1: backward scalars.  BLOCK = false: one range item of short
+// rows per wavefront; BLOCK = true: one long row per workgroup.
+template <int MODE, bool BLOCK>
+__global__ __launch_bounds__(kBlock) void k_gat_rows(const GatRows g, float* __restrict__ att,
+                                                     float* __restrict__ dal, float* __restrict__ gs_dst_own)
+{
+    __shared__ float sm[kBlock / kWave];
+    if (BLOCK) {
+        const int64_t i = blockIdx.x;
+        if (i >= g.nlong) return;
+        const int32_t row = g.long_row[i];
+        if (MODE == 0) att_row<true>(g, row, att, sm);
+        else bwd_row<true>(g, row, att, dal, gs_dst_own, sm);
+    } else {
+        const int64_t item = (int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;
+        if (item >= g.nranges) return;
+        const int32_t r1 = g.range_rows[item + 1];
+        for (int32_t row = g.range_rows[item]; row < r1; ++row) {
+            if (g.rp[row + 1] - g.rp[row] > kSpmmSegment) continue;     // long row: its own workgroup
+            if (MODE == 0) att_row<false>(g, row, att, sm);
+            else bwd_row<false>(g, row, att, dal, gs_dst_own, sm);
+        }
+    }
+}
+
+// Rows of the transposed operator (the entries of R_p = [own ; boundary] as sources):
+// tw_att[pos - e0] = att[tperm[pos]] (entry weights of the transposed aggregation) and
+// gs_src[owner row of i] += sum over the row of dpre[tperm[pos]].
+struct GatTRows {
+    const int64_t* trp;
+    const int32_t* tperm;
+    int64_t e0;
+    int64_t n_own, base_row;
+    const int32_t* bnd;         // library rows of the boundary vertices
+    const int32_t* range_rows;
+    int64_t nranges;
+    const int32_t* long_row;
+    int64_t nlong;
+};
+template <bool BLOCK>
+__device__ inline void trow(const GatTRows& g, int32_t i, const float* __restrict__ att,
+                            const float* __restrict__ dpre, float* __restrict__ tw_att,
+                            float* __restrict__ gs_src, float* sm)
+{
+    constexpr int T = BLOCK ? kBlock : kWave;
+    const int t = BLOCK ? threadIdx.x : threadIdx.x % kWave;
+    const int64_t eb = g.trp[i], ee = g.trp[i + 1];
+    float s = 0.f;
+    for (int64_t e = eb + t; e < ee; e += T) {
+        const int32_t fe = g.tperm[e];
+        tw_att[e - g.e0] = att[fe];
+        if (dpre) s += dpre[fe];
+    }
+    if (!dpre) return;
+    s = red_sum<BLOCK>(s, sm);
+    if (t == 0) {
+        const int64_t r = i < g.n_own ? g.base_row + i : (int64_t)g.bnd[i - g.n_own];
+        gs_src[r] += s;
+    }
+}
+template <bool BLOCK>
+__global__ __launch_bounds__(kBlock) void k_gat_trows(const GatTRows g, const float* __restrict__ att,
+                                                      const float* __restrict__ dpre,
+                                                      float* __restrict__ tw_att, float* __restrict__ gs_src)
+{
+    __shared__ float sm[kBlock / kWave];
+    if (BLOCK) {
+        const int64_t i = blockIdx.x;
+        if (i >= g.nlong) return;
+        trow<true>(g, g.long_row[i], att, dpre, tw_att, gs_src, sm);
+    } else {
+        const int64_t item = (int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;
+        if (item >= g.nranges) return;
+        const int32_t r1 = g.range_rows[item + 1];
+        for (int32_t i = g.range_rows[item]; i < r1; ++i) {
+            if (g.trp[i + 1] - g.trp[i] > kSpmmSegment) continue;
+            trow<false>(g, i, att, dpre, tw_att, gs_src, sm);
+        }
+    }
+}
+
+// Edge-wise dot products: dal[e - e0] = dY[row,:] . src(col[e])[:] with src the partition's own
+// rows of H or the staged boundary rows.  One wavefront per work item (a segment of a long row
+// or a range of short rows); the 64 lanes form 64 / G slots of G lanes, a slot handles one entry
+// at a time with NV 16-byte vectors per lane and sums its G partial products with shuffles.
+struct GatDotArgs {
+    const int64_t* rp;
+    const int32_t* col;
+    int64_t e0, n_own;
+    const float* a_rows;
+    const float* b_rows;
+    const float* dy;            // [n_own, ld]
+    int32_t ld;                 // row stride of H, staging and dy (multiple of 4)
+    float* dal;
+    SpmmItems it;
+};
+template <int G, int NV>
+__device__ inline void dot_entries(const GatDotArgs& g, int32_t row, int64_t eb, int64_t ee, int lane)
+{
+    constexpr int S = kWave / G;
+    constexpr int U = 4;
+    const int slot = lane / G, gl = lane % G;
+    float4 y[NV];
+    int cv[NV];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+        const int c = (v * G + gl) * 4;
+        cv[v] = c < g.ld ? c : -1;
+        y[v] = cv[v] >= 0 ? *reinterpret_cast<const float4*>(g.dy + (int64_t)row * g.ld + c)
+                          : make_float4(0.f, 0.f, 0.f, 0.f);
+        if (cv[v] < 0) cv[v] = 0;
+    }
+    for (int64_t e = eb; e < ee; e += S * U) {
+        float acc[U];
+        const float* src[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t ee_u = e + u * S + slot;
+            const int64_t ec = ee_u < ee ? ee_u : ee - 1;
+            const int32_t c = g.col[ec];
+            src[u] = c < g.n_own ? g.a_rows + (int64_t)c * g.ld : g.b_rows + ((int64_t)c - g.n_own) * g.ld;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            acc[u] = 0.f;
+#pragma unroll
+            for (int v = 0; v < NV; ++v) {
+                const float4 h = *reinterpret_cast<const float4*>(src[u] + cv[v]);
+                acc[u] += (h.x * y[v].x + h.y * y[v].y) + (h.z * y[v].z + h.w * y[v].w);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float a = acc[u];
+#pragma unroll
+            for (int m = 1; m < G; m <<= 1) a += __shfl_xor(a, m, kWave);
+            const int64_t ee_u = e + u * S + slot;
+            if (gl == 0 && ee_u < ee) g.dal[ee_u - g.e0] = a;
+        }
+    }
+}
+template <int G, int NV>
+__global__ __launch_bounds__(kBlock) void k_gat_dots(const GatDotArgs g)
+{
+    const int lane = threadIdx.x % kWave;
+    const int64_t item = (int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;
+    if (item < g.it.nsegs) {
+        const int64_t eb = g.it.seg_begin[item];
+        dot_entries<G, NV>(g, g.it.seg_row[item], eb, eb + g.it.seg_len[item], lane);
+        return;
+    }
+    const int64_t ri = item - g.it.nsegs;
+    if (ri >= g.it.nranges) return;
+    const int32_t r1 = g.it.range_rows[ri + 1];
+    for (int32_t row = g.it.range_rows[ri]; row < r1; ++row) {
+        const int64_t eb = g.rp[row], ee = g.rp[row + 1];
+        if (ee - eb > kSpmmSegment) continue;
+        dot_entries<G, NV>(g, row, eb, ee, lane);
+    }
+}
+
+// gH[r, j] += gs_src[r] a_src[j] + gs_dst[r] a_dst[j] for the rows of one partition, and the
+// per-block partial column sums  sum_r gs_src[r] H[r, j]  (first f columns of `partial` rows) and
+// sum_r gs_dst[r] H[r, j]  (next f columns), 256 rows per block.
+__global__ __launch_bounds__(kBlock) void k_gat_rank1(float* __restrict__ gH, const float* __restrict__ H,
+                                                      int32_t ld, int32_t f, int64_t rows,
+                                                      const float* __restrict__ gs_src,
+                                                      const float* __restrict__ gs_dst,
+                                                      const float* __restrict__ a_src,
+                                                      const float* __restrict__ a_dst,
+                                                      float* __restrict__ partial)
+{
+    const int64_t r0 = (int64_t)blockIdx.x * 256;
+    const int64_t r1 = r0 + 256 < rows ? r0 + 256 : rows;
+    for (int32_t j = threadIdx.x; j < f; j += kBlock) {
+        const float as = a_src[j], ad = a_dst[j];
+        float p1 = 0.f, p2 = 0.f;
+        for (int64_t r = r0; r < r1; ++r) {
+            const float gs = gs_src[r], gd = gs_dst[r];
+            const float h = H[r * ld + j];
+            gH[r * ld + j] += gs * as + gd * ad;
+            p1 += gs * h;
+            p2 += gd * h;
+        }
+        partial[(int64_t)blockIdx.x * 2 * f + j] = p1;
+        partial[(int64_t)blockIdx.x * 2 * f + f + j] = p2;
+    }
+}
+
+}  // namespace
+
+void launch_gat_scores(const float* H, int32_t ld, int32_t f, int64_t rows, const float* a_src,
+                       const float* a_dst, float* ssrc, float* sdst, hipStream_t s)
+{
+    if (rows <= 0) return;
+    const int64_t blocks = (rows + kBlock / kWave - 1) / (kBlock / kWave);
+    hipLaunchKernelGGL(k_gat_scores, dim3((unsigned)blocks), dim3(kBlock), 0, s, H, ld, f, rows, a_src, a_dst,
+                       ssrc, sdst);
+}
+
+static GatRows make_rows(const GatRowsHost& h)
+{
+    GatRows g;
+    g.rp = h.rp; g.col = h.col; g.e0 = h.e0; g.n_own = h.n_own;
+    g.ssrc_own = h.ssrc_own; g.ssrc_bnd = h.ssrc_bnd; g.sdst_own = h.sdst_own;
+    g.range_rows = h.items.range_rows; g.nranges = h.items.nranges;
+    g.long_row = h.items.long_row; g.nlong = h.items.nlong;
+    return g;
+}
+
+void launch_gat_attention(const GatRowsHost& h, float* att, hipStream_t s)
+{
+    const GatRows g = make_rows(h);
+    if (g.nranges > 0)
+        hipLaunchKernelGGL((k_gat_rows<0, false>), dim3((unsigned)((g.nranges + 3) / 4)), dim3(kBlock), 0, s, g,
+                           att, (float*)nullptr, (float*)nullptr);
+    if (g.nlong > 0)
+        hipLaunchKernelGGL((k_gat_rows<0, true>), dim3((unsigned)g.nlong), dim3(kBlock), 0, s, g, att,
+                           (float*)nullptr, (float*)nullptr);
+}
+
+void launch_gat_bwd_scalars(const GatRowsHost& h, const float* att, float* dal, float* gs_dst_own, hipStream_t s)
+{
+    const GatRows g = make_rows(h);
+    if (g.nranges > 0)
+        hipLaunchKernelGGL((k_gat_rows<1, false>), dim3((unsigned)((g.nranges + 3) / 4)), dim3(kBlock), 0, s, g,
+                           const_cast<float*>(att), dal, gs_dst_own);
+    if (g.nlong > 0)
+        hipLaunchKernelGGL((k_gat_rows<1, true>), dim3((unsigned)g.nlong), dim3(kBlock), 0, s, g,
+                           const_cast<float*>(att), dal, gs_dst_own);
+}
+
+void launch_gat_transposed(const int64_t* trp, const int32_t* tperm, int64_t e0, int64_t n_own,
+                           int64_t base_row, const int32_t* bnd, const SpmmItems& items, const float* att,
+                           const float* dpre, float* tw_att, float* gs_src, hipStream_t s)
+{
+    GatTRows g;
+    g.trp = trp; g.tperm = tperm; g.e0 = e0; g.n_own = n_own; g.base_row = base_row; g.bnd = bnd;
+    g.range_rows = items.range_rows; g.nranges = items.nranges;
+    g.long_row = items.long_row; g.nlong = items.nlong;
+    if (g.nranges > 0)
+        hipLaunchKernelGGL((k_gat_trows<false>), dim3((unsigned)((g.nranges + 3) / 4)), dim3(kBlock), 0, s, g, att,
+                           dpre, tw_att, gs_src);
+    if (g.nlong > 0)
+        hipLaunchKernelGGL((k_gat_trows<true>), dim3((unsigned)g.nlong), dim3(kBlock), 0, s, g, att, dpre, tw_att,
+                           gs_src);
+}
+
+void launch_gat_dots(const int64_t* rp, const int32_t* col, int64_t e0, int64_t n_own, const float* a_rows,
+                     const float* b_rows, const float* dy, int32_t ld, float* dal, const SpmmItems& items,
+                     hipStream_t s)
+{
+    const int64_t nitems = items.nsegs + items.nranges;
+    if (nitems <= 0) return;
+    GatDotArgs g;
+    g.rp = rp; g.col = col; g.e0 = e0; g.n_own = n_own; g.a_rows = a_rows; g.b_rows = b_rows; g.dy = dy;
+    g.ld = ld; g.dal = dal; g.it = items;
+    const dim3 grid((unsigned)((nitems + 3) / 4)), block(kBlock);
+    const int vecs = ld / 4;
+    if (vecs <= 4) hipLaunchKernelGGL((k_gat_dots<4, 1>), grid, block, 0, s, g);
+    else if (vecs <= 8) hipLaunchKernelGGL((k_gat_dots<8, 1>), grid, block, 0, s, g);
+    else if (vecs <= 16) hipLaunchKernelGGL((k_gat_dots<16, 1>), grid, block, 0, s, g);
+    else if (vecs <= 32) hipLaunchKernelGGL((k_gat_dots<32, 1>), grid, block, 0, s, g);
+    else if (vecs <= 64) hipLaunchKernelGGL((k_gat_dots<64, 1>), grid, block, 0, s, g);
+    else if (vecs <= 128) hipLaunchKernelGGL((k_gat_dots<64, 2>), grid, block, 0, s, g);
+    else hipLaunchKernelGGL((k_gat_dots<64, 4>), grid, block, 0, s, g);
+}
+
+int64_t gat_rank1_partial_floats(int64_t rows, int32_t f) { return ((rows + 255) / 256) * 2 * (int64_t)f; }
+
+void launch_gat_rank1(float* gH, const float* H, int32_t ld, int32_t f, int64_t rows, const float* gs_src,
+                      const float* gs_dst, const float* a_src, const float* a_dst, float* partial, hipStream_t s)
+{
+    if (rows <= 0) return;
+    hipLaunchKernelGGL(k_gat_rank1, dim3((unsigned)((rows + 255) / 256)), dim3(kBlock), 0, s, gH, H, ld, f, rows,
+                       gs_src, gs_dst, a_src, a_dst, partial);
+}
+
+}  // namespace gnnmi

@@ -499,12 +499,16 @@ gnn_status build_host_meta(int model, int64_t n, const int64_t* rowptr, const in
         }
 
         // ---- operator rows: A + I for GCN (one self-loop each), A for SAGE ----------------
+        // GCN: A + I with symmetric-normalisation weights; GAT: the structure of A + I, weights
+        // come from the attention at run time; SAGE: A with 1/in-degree row scales
+        const bool gat = (model == GNN_GAT);
+        const bool self_loops = (model == GNN_GCN) || gat;
         const bool gcn = (model == GNN_GCN);
         std::vector<int32_t> opdeg((size_t)n);       // by original id
         std::vector<uint8_t> add_self((size_t)n, 0);  // by original id
         parallel_for(n, 8192, [&](int, int64_t v) {
             int64_t len = rowptr[v + 1] - rowptr[v];
-            if (gcn) {
+            if (self_loops) {
                 const int32_t* b = colidx + rowptr[v];
                 bool has = std::binary_search(b, b + len, (int32_t)v);
                 add_self[(size_t)v] = has ? 0 : 1;
@@ -518,7 +522,7 @@ gnn_status build_host_meta(int model, int64_t n, const int64_t* rowptr, const in
         const int64_t nnz = M.rp[(size_t)n];
         M.lcol.resize((size_t)nnz);
         if (gcn) M.ew.resize((size_t)nnz);
-        else {
+        else if (!gat) {
             M.rscale.resize((size_t)n);
             for (int64_t r = 0; r < n; ++r) {
                 int32_t dg = opdeg[(size_t)M.order[(size_t)r]];
@@ -561,7 +565,7 @@ gnn_status build_host_meta(int model, int64_t n, const int64_t* rowptr, const in
                     row.emplace_back(lc, w);
                 };
                 for (int64_t e = rowptr[v]; e < rowptr[v + 1]; ++e) push(colidx[e]);
-                if (gcn && add_self[(size_t)v]) push(v);
+                if (self_loops && add_self[(size_t)v]) push(v);
                 std::sort(row.begin(), row.end(),
                           [](const std::pair<int32_t, float>& a, const std::pair<int32_t, float>& b) {
                               return a.first < b.first;
@@ -661,7 +665,8 @@ gnn_status build_host_meta(int model, int64_t n, const int64_t* rowptr, const in
         // ---- phase C: transpose of every T_p ------------------------------------------------
         M.trp.assign((size_t)M.toff[(size_t)k] + 1, 0);
         M.tcol.resize((size_t)nnz);
-        M.tw.resize((size_t)nnz);
+        if (gat) M.tperm.resize((size_t)nnz);
+        else M.tw.resize((size_t)nnz);
         std::vector<int64_t> required((size_t)k, 0);
         parallel_for(k, 1, [&](int, int64_t p) {
             const int64_t r0 = M.off[(size_t)p], r1 = M.off[(size_t)p + 1];
@@ -679,11 +684,12 @@ gnn_status build_host_meta(int model, int64_t n, const int64_t* rowptr, const in
             for (int64_t i = 0; i < nR; ++i) trp[i] = e0 + cursor[(size_t)i];
             if (p == k - 1) trp[nR] = e1;
             for (int64_t r = r0; r < r1; ++r) {
-                const float rs = gcn ? 1.0f : M.rscale[(size_t)r];
+                const float rs = (gcn || gat) ? 1.0f : M.rscale[(size_t)r];
                 for (int64_t e = M.rp[(size_t)r]; e < M.rp[(size_t)r + 1]; ++e) {
                     int64_t pos = e0 + cursor[(size_t)M.lcol[(size_t)e]]++;
                     M.tcol[(size_t)pos] = (int32_t)(r - r0);
-                    M.tw[(size_t)pos] = gcn ? M.ew[(size_t)e] : rs;
+                    if (gat) M.tperm[(size_t)pos] = (int32_t)(e - e0);
+                    else M.tw[(size_t)pos] = gcn ? M.ew[(size_t)e] : rs;
                 }
             }
         });

@@ -504,3 +504,60 @@ def test_transform_first_layers_match_oracle(name, dims):
     # the default order is untouched by all this
     s0 = Session(model, dims, rowptr, colidx, k, cfg["part"], cfg["seed"], X, w, y, m)
     assert not any(s0.ctx.layer_is_transform_first(l) for l in range(1, L + 1))
+
+
+# ----------------------------------------------------------------------------------------
+# graph attention
+# ----------------------------------------------------------------------------------------
+def gat_weights(dims, seed):
+    rng = np.random.default_rng(seed)
+    w = []
+    for l in range(len(dims) - 1):
+        w.append({"W": (rng.standard_normal((dims[l], dims[l + 1])) / np.sqrt(dims[l])).astype(np.float32),
+                  "a_src": (rng.standard_normal(dims[l + 1]) * 0.5).astype(np.float32),
+                  "a_dst": (rng.standard_normal(dims[l + 1]) * 0.5).astype(np.float32),
+                  "b": (rng.standard_normal(dims[l + 1]) * 0.1).astype(np.float32)})
+    return w
+
+
+@pytest.mark.parametrize("name,dims,k,mode", [("mini_sage", (24, 32, 16, 7), 5, "lp"),
+                                              ("mini_gcn_directed", (20, 9, 12, 5), 7, "random"),
+                                              ("tiny", (64, 64, 16), 4, "switching"),
+                                              ("mini_sage", (24, 260, 7), 1, "random")])
+def test_graph_attention_epoch_matches_oracle(name, dims, k, mode):
+    say("case graph attention %s %s k=%d" % (name, dims, k))
+    import torch
+    from oracle import gat as ogat
+    from paper_2605_11517_amd import Session
+    cfg, rowptr, colidx = make_config(name, dims=dims)
+    n = cfg["n"]
+    L = len(dims) - 1
+    X = features(n, dims[0], cfg["seed"])
+    y, m = labels_and_mask(n, dims[-1], cfg["train_frac"], cfg["seed"])
+    w = gat_weights(dims, cfg["seed"])
+    ref = ogat.epoch(rowptr, colidx, dims, X, w, y, m)
+    s = Session("gat", dims, rowptr, colidx, k, mode, cfg["seed"], X, w, y, m)
+    assert all(s.ctx.layer_is_transform_first(l) for l in range(1, L + 1))
+    loss = s.epoch()
+    assert abs(loss - ref["loss"]) <= TOL * abs(ref["loss"]), (loss, ref["loss"])
+    got = s.results()
+    worst = {}
+    for l in range(L):
+        worst["act[%d]" % l] = rel_err(got["act"][l], ref["act"][l])
+        worst["gact[%d]" % l] = rel_err(got["gact"][l], ref["gact"][l])
+        worst["gW[%d]" % l] = rel_err(got["gW"][l], ref["gW"][l])
+        # the two attention-vector gradients share a scale (ga_dst can vanish identically: the
+        # softmax gradient of a destination sums to zero wherever its scores share a sign)
+        ga_ref = np.stack([ref["ga_src"][l], ref["ga_dst"][l]])
+        worst["ga[%d]" % l] = rel_err(got["gWs"][l], ga_ref)
+        worst["gb[%d]" % l] = rel_err(got["gb"][l], ref["gb"][l])
+    say("  worst rel err %.3g" % max(worst.values()))
+    bad = {key: v for key, v in worst.items() if not (v <= TOL)}
+    assert not bad, bad
+    # a second epoch gives the same bits, and three Adam steps follow the oracle
+    r1 = s.results()
+    assert s.epoch() == loss
+    r2 = s.results()
+    for key in ("act", "gact", "gW", "gWs", "gb"):
+        for a, b in zip(r1[key], r2[key]):
+            assert np.array_equal(a, b), key
