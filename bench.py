@@ -39,14 +39,18 @@ def algorithmic_bytes(stats, dims, model, n_parts, es=4, fused_scatter=False, xf
     sum_r = n + stats["sum_boundary"]            # sum over partitions of |own_p| + |B_p|
     sum_b = stats["sum_boundary"]
     L = len(dims) - 1
-    per_entry = 4 + (4 if model == "gcn" else 0)  # column index (+ stored weight for GCN)
+    per_entry = 4 + (4 if model in ("gcn", "gat") else 0)  # column index (+ entry weight: GCN, GAT)
     out = {"gather": 0, "spmm": 0, "spmm_t": 0, "scatter": 0}
     xf = xf or [False] * L
     for l in range(1, L + 1):
         if xf[l - 1]:
             row = (dims[l] + 3) // 4 * 4 * 4
-            out["gather"] += 2 * sum_b * row + 4 * sum_b
-            out["spmm"] += per_entry * nnz + 8 * (n + k) + sum_r * row + n * row + (4 * n if model == "sage" else 0)
+            one_gather = 2 * sum_b * row + 4 * sum_b
+            one_spmm = per_entry * nnz + 8 * (n + k) + sum_r * row + n * row + (4 * n if model == "sage" else 0)
+            # graph attention regathers, and reads every needed row once more for the edge-wise
+            # products dY[v] . H[u] (same traffic as an aggregation, 4 bytes written per entry)
+            out["gather"] += one_gather * (2 if model == "gat" else 1)
+            out["spmm"] += one_spmm * (2 if model == "gat" else 1)
             out["spmm_t"] += 8 * nnz + 8 * (sum_r + k) + n * row + 2 * sum_r * row + 4 * sum_b
             continue
         d = dims[l - 1]
@@ -89,9 +93,14 @@ def _oracle_epoch_seconds(cfg, n):
     y, m = labels_and_mask(n, dims[-1], cfg["train_frac"], cfg["seed"])
     w = glorot_weights(dims, cfg["seed"], sage=(cfg["model"] == "sage"))
     t0 = time.perf_counter()
-    og.epoch(cfg["model"], rowptr, colidx, dims, X, w, y, m)
+    if cfg["model"] == "gat":
+        from oracle import gat as ogat
+        from synth import attention_vectors
+        ogat.epoch(rowptr, colidx, dims, X, attention_vectors(w, cfg["seed"]), y, m)
+    else:
+        og.epoch(cfg["model"], rowptr, colidx, dims, X, w, y, m)
     dt = time.perf_counter() - t0
-    nnz = int(rowptr[-1]) + (n if cfg["model"] == "gcn" and not cfg["self_loops"] else 0)
+    nnz = int(rowptr[-1]) + (n if cfg["model"] in ("gcn", "gat") and not cfg["self_loops"] else 0)
     return dt, nnz
 
 
@@ -101,7 +110,7 @@ def cpu_baseline(cfg, scale_n, log_fn):
     probe run picks the sample size that gives roughly 15 s of CPU work on this machine."""
     from oracle import fullgraph as og
     if scale_n <= 0:
-        probe_n = max(2000, min(cfg["n"], 20000))
+        probe_n = max(2000, min(cfg["n"], 2000 if cfg["model"] == "gat" else 20000))
         dt, _ = _oracle_epoch_seconds(cfg, probe_n)
         scale_n = int(max(probe_n, min(cfg["n"], 1_000_000, probe_n * 15.0 / max(dt, 1e-3))))
         log_fn("cpu oracle probe: n=%d took %.2f s -> sample n=%d" % (probe_n, dt, scale_n))
@@ -142,7 +151,7 @@ def main():
     import numpy as np
     import torch
     from paper_2605_11517_amd import Session
-    from synth import CONFIGS, features, glorot_weights, labels_and_mask, make_config
+    from synth import CONFIGS, attention_vectors, features, glorot_weights, labels_and_mask, make_config
 
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
@@ -154,6 +163,8 @@ def main():
     X = features(n, dims[0], cfg["seed"])
     y, m = labels_and_mask(n, dims[-1], cfg["train_frac"], cfg["seed"])
     w = glorot_weights(dims, cfg["seed"], sage=(model == "sage"))
+    if model == "gat":
+        attention_vectors(w, cfg["seed"])
     t1 = time.perf_counter()
     if args.partitioner:
         cfg["part"] = args.partitioner
@@ -230,6 +241,8 @@ def main():
         out["kernel_classes"] = classes
         sp_ms, sp_launches = prof["spmm"]
         passes = sum(1 if t else 2 for t in xf)       # forward (+ recompute) aggregations
+        if model == "gat":
+            passes = 2 * len(xf)                        # aggregation + edge-wise products
         tp_ms = prof["spmm_t"][0]
         transposed = (len(dims) - 2) + (1 if xf[0] else 0)   # a transform-first layer 1 still pushes grad H
         out["aggregated_edges_per_s"] = nnz * (passes + transposed) * args.steps / ((sp_ms + tp_ms) * 1e-3)
@@ -253,7 +266,7 @@ def main():
         for l in range(L):
             if xf[l]:
                 roww = (dims[l + 1] + 3) // 4 * 4 * 4
-                upper += 2 * (stats["nnz"] * (4 + roww) + n * roww)
+                upper += (3 if model == "gat" else 2) * (stats["nnz"] * (4 + roww) + n * roww)
             else:
                 upper += (2 if l == 0 else 3) * (stats["nnz"] * (4 + dims[l] * es) + n * dims[l] * es)
         out["roofline"] = {

@@ -102,7 +102,7 @@ void gat_layer_fwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
     const GatRowsHost rows = rows_of(c, v, p);
     {
         Timed t(c, s, GNN_K_OTHER);
-        launch_gat_attention(rows, v.att, s);
+        launch_gat_attention(rows, v.att, (float*)(c->scratch + c->ws.segpart), s);
     }
     float* Z = (float*)(c->scratch + c->ws.z);
     float* segpart = (float*)(c->scratch + c->ws.segpart);
@@ -162,7 +162,7 @@ void gat_layer_bwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
     {
         // recompute the attention weights from the regathered scores
         Timed t(c, s, GNN_K_OTHER);
-        launch_gat_attention(rows, v.att, s);
+        launch_gat_attention(rows, v.att, (float*)(c->scratch + c->ws.segpart), s);
     }
     {
         Timed t(c, s, GNN_K_SPMM);      // edge-wise products: one source row read per entry
@@ -174,7 +174,7 @@ void gat_layer_bwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
     const int32_t* bnd = c->D.bnd + M.boff[(size_t)p];
     {
         Timed t(c, s, GNN_K_OTHER);
-        launch_gat_bwd_scalars(rows, v.att, v.dal, v.gsdst + v.r0, s);
+        launch_gat_bwd_scalars(rows, v.att, v.dal, v.gsdst + v.r0, (float*)(c->scratch + c->ws.segpart), s);
         launch_gat_transposed(c->D.trp + t0, c->D.tperm, v.e0, v.np, v.r0, bnd, titems, v.att, v.dal, v.twatt,
                               v.gssrc, s);
     }

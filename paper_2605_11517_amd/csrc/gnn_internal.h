@@ -218,13 +218,15 @@ struct GatRowsHost {
 void launch_gat_scores(const float* H, int32_t ld, int32_t f, int64_t rows, const float* a_src,
                        const float* a_dst, float* ssrc, float* sdst, hipStream_t s);
 // att[e - e0] = softmax over each row of LeakyReLU_0.2(s_src(col e) + s_dst(row))
-void launch_gat_attention(const GatRowsHost& h, float* att, hipStream_t s);
+// segwork: 3 floats per segment of the partition's long rows (scratch of the segment-parallel passes)
+void launch_gat_attention(const GatRowsHost& h, float* att, float* segwork, hipStream_t s);
 // dal[e - e0] = dy[row,:] . src(col e)[:]  (rows of width ld, a multiple of 4)
 void launch_gat_dots(const int64_t* rp, const int32_t* col, int64_t e0, int64_t n_own, const float* a_rows,
                      const float* b_rows, const float* dy, int32_t ld, float* dal, const SpmmItems& items,
                      hipStream_t s);
 // dal <- gradient of the pre-activation scores (through softmax and LeakyReLU); gs_dst_own[row] = row sum
-void launch_gat_bwd_scalars(const GatRowsHost& h, const float* att, float* dal, float* gs_dst_own, hipStream_t s);
+void launch_gat_bwd_scalars(const GatRowsHost& h, const float* att, float* dal, float* gs_dst_own,
+                            float* segwork, hipStream_t s);
 // transposed rows: tw_att[pos - e0] = att[tperm[pos]]; with dpre != null also
 // gs_src[owner row of transposed row i] += sum over the row of dpre[tperm[pos]]
 void launch_gat_transposed(const int64_t* trp, const int32_t* tperm, int64_t e0, int64_t n_own,

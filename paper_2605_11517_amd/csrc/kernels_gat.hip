@@ -6,9 +6,10 @@
 // attention weights as entry weights).  The backward pass regathers, recomputes the attention
 // weights and needs one more edge-wise kernel: the dot product dY[v] . H[u] per entry.
 //
-// Row-wise scalar passes come in two shapes: a wavefront walks the short rows of a range item
-// one after the other; a whole workgroup cooperates on one long row.  All reductions are
-// shuffles and fixed-order LDS sums, so results are reproducible.
+// Row-wise scalar passes: a wavefront walks the short rows of a range item one after the other;
+// long rows are cut into the aggregation kernel's segments, one wavefront per segment, and
+// combined per row in segment order.  All reductions are shuffles and fixed-order sums, so
+// results are reproducible.
 #include "gnn_internal.h"
 
 namespace gnnmi {
@@ -40,16 +41,6 @@ template <bool BLOCK> __device__ inline float red_sum(float v, float* sm)
     __syncthreads();
     return (sm[0] + sm[1]) + (sm[2] + sm[3]);
 }
-template <bool BLOCK> __device__ inline float red_max(float v, float* sm)
-{
-    v = wave_max(v);
-    if (!BLOCK) return v;
-    __syncthreads();
-    if (threadIdx.x % kWave == 0) sm[threadIdx.x / kWave] = v;
-    __syncthreads();
-    return fmaxf(fmaxf(sm[0], sm[1]), fmaxf(sm[2], sm[3]));
-}
-
 struct GatRows {
     const int64_t* rp;          // row pointers of the partition's rows (absolute positions)
     const int32_t* col;         // local columns (absolute positions)
@@ -91,71 +82,210 @@ __global__ __launch_bounds__(kBlock) void k_gat_scores(const float* __restrict__
     }
 }
 
-// attention weights of one row: att[e - e0] = softmax over the row's entries of
-// LeakyReLU(s_src(col) + s_dst(row))
-template <bool BLOCK>
-__device__ inline void att_row(const GatRows& g, int32_t row, float* __restrict__ att, float* sm)
+// attention weights of one short row (at most kSpmmSegment = 8 x 64 entries):
+// att[e - e0] = softmax over the row's entries of LeakyReLU(s_src(col) + s_dst(row)).  Every
+// lane keeps its up to eight scores in registers, so the scores are gathered once.
+constexpr int kPerLane = kSpmmSegment / kWave;
+
+__device__ inline void att_row_wave(const GatRows& g, int32_t row, float* __restrict__ att)
 {
-    constexpr int T = BLOCK ? kBlock : kWave;
-    const int t = BLOCK ? threadIdx.x : threadIdx.x % kWave;
+    const int t = threadIdx.x % kWave;
     const int64_t eb = g.rp[row], ee = g.rp[row + 1];
+    const int niter = (int)((ee - eb + kWave - 1) / kWave);
     const float sd = g.sdst_own[row];
+    float x[kPerLane];
     float m = -INFINITY;
-    for (int64_t e = eb + t; e < ee; e += T) m = fmaxf(m, lrelu(g.ssrc(g.col[e]) + sd));
-    m = red_max<BLOCK>(m, sm);
+#pragma unroll
+    for (int i = 0; i < kPerLane; ++i) {
+        x[i] = -INFINITY;
+        if (i < niter) {
+            const int64_t e = eb + t + (int64_t)i * kWave;
+            if (e < ee) x[i] = lrelu(g.ssrc(g.col[e]) + sd);
+            m = fmaxf(m, x[i]);
+        }
+    }
+    m = wave_max(m);
     float s = 0.f;
-    for (int64_t e = eb + t; e < ee; e += T) s += expf(lrelu(g.ssrc(g.col[e]) + sd) - m);
-    s = red_sum<BLOCK>(s, sm);
+#pragma unroll
+    for (int i = 0; i < kPerLane; ++i)
+        if (i < niter) {
+            x[i] = expf(x[i] - m);          // exp(-inf) = 0 for the lanes past the row end
+            s += x[i];
+        }
+    s = wave_sum(s);
     const float inv = 1.f / s;
-    for (int64_t e = eb + t; e < ee; e += T) att[e - g.e0] = expf(lrelu(g.ssrc(g.col[e]) + sd) - m) * inv;
+#pragma unroll
+    for (int i = 0; i < kPerLane; ++i)
+        if (i < niter) {
+            const int64_t e = eb + t + (int64_t)i * kWave;
+            if (e < ee) att[e - g.e0] = x[i] * inv;
+        }
 }
 
 // after the edge-wise dot products dal[e] = dY[row] . H[col]: t = sum att dal;
 // dal[e] <- att (dal - t) LeakyReLU'(x)  (gradient of the pre-activation score);
 // gs_dst[row] = sum of those
-template <bool BLOCK>
-__device__ inline void bwd_row(const GatRows& g, int32_t row, const float* __restrict__ att,
-                               float* __restrict__ dal, float* __restrict__ gs_dst_own, float* sm)
+__device__ inline void bwd_row_wave(const GatRows& g, int32_t row, const float* __restrict__ att,
+                                    float* __restrict__ dal, float* __restrict__ gs_dst_own)
 {
-    constexpr int T = BLOCK ? kBlock : kWave;
-    const int t = BLOCK ? threadIdx.x : threadIdx.x % kWave;
+    const int t = threadIdx.x % kWave;
     const int64_t eb = g.rp[row], ee = g.rp[row + 1];
+    const int niter = (int)((ee - eb + kWave - 1) / kWave);
     const float sd = g.sdst_own[row];
+    float a[kPerLane], d[kPerLane], sl[kPerLane];
     float tv = 0.f;
-    for (int64_t e = eb + t; e < ee; e += T) tv += att[e - g.e0] * dal[e - g.e0];
-    tv = red_sum<BLOCK>(tv, sm);
-    float ds = 0.f;
-    for (int64_t e = eb + t; e < ee; e += T) {
-        const float x = g.ssrc(g.col[e]) + sd;
-        const float dp = att[e - g.e0] * (dal[e - g.e0] - tv) * (x > 0.f ? 1.f : kSlope);
-        dal[e - g.e0] = dp;
-        ds += dp;
+#pragma unroll
+    for (int i = 0; i < kPerLane; ++i) {
+        a[i] = 0.f; d[i] = 0.f; sl[i] = 0.f;
+        if (i < niter) {
+            const int64_t e = eb + t + (int64_t)i * kWave;
+            if (e < ee) {
+                a[i] = att[e - g.e0];
+                d[i] = dal[e - g.e0];
+                sl[i] = (g.ssrc(g.col[e]) + sd) > 0.f ? 1.f : kSlope;
+            }
+            tv += a[i] * d[i];
+        }
     }
-    ds = red_sum<BLOCK>(ds, sm);
+    tv = wave_sum(tv);
+    float ds = 0.f;
+#pragma unroll
+    for (int i = 0; i < kPerLane; ++i)
+        if (i < niter) {
+            const int64_t e = eb + t + (int64_t)i * kWave;
+            const float dp = a[i] * (d[i] - tv) * sl[i];
+            if (e < ee) dal[e - g.e0] = dp;
+            ds += dp;
+        }
+    ds = wave_sum(ds);
     if (t == 0) gs_dst_own[row] = ds;
 }
 
-// MODE 0: attention weights; MODE 1: backward scalars.  BLOCK = false: one range item of short
-// rows per wavefront; BLOCK = true: one long row per workgroup.
-template <int MODE, bool BLOCK>
+// MODE 0: attention weights; MODE 1: backward scalars.  One range item of short rows per
+// wavefront; long rows are skipped here and handled segment by segment below.
+template <int MODE>
 __global__ __launch_bounds__(kBlock) void k_gat_rows(const GatRows g, float* __restrict__ att,
                                                      float* __restrict__ dal, float* __restrict__ gs_dst_own)
 {
-    __shared__ float sm[kBlock / kWave];
-    if (BLOCK) {
-        const int64_t i = blockIdx.x;
-        if (i >= g.nlong) return;
-        const int32_t row = g.long_row[i];
-        if (MODE == 0) att_row<true>(g, row, att, sm);
-        else bwd_row<true>(g, row, att, dal, gs_dst_own, sm);
+    const int64_t item = (int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;
+    if (item >= g.nranges) return;
+    const int32_t r1 = g.range_rows[item + 1];
+    for (int32_t row = g.range_rows[item]; row < r1; ++row) {
+        if (g.rp[row + 1] - g.rp[row] > kSpmmSegment) continue;
+        if (MODE == 0) att_row_wave(g, row, att);
+        else bwd_row_wave(g, row, att, dal, gs_dst_own);
+    }
+}
+
+// ---- long rows, segment-parallel --------------------------------------------------------------
+// A long row is cut into segments of at most kSpmmSegment entries (the aggregation kernel's work
+// items); one wavefront handles one segment with its entries in registers, a second small
+// kernel combines the segments of each row in segment order, a third applies the result.
+struct GatSegs {
+    const int32_t* seg_row;
+    const int64_t* seg_begin;
+    const int32_t* seg_len;
+    int64_t nsegs;
+    const int32_t* long_row;
+    const int32_t* long_first;
+    const int32_t* long_nseg;
+    int64_t nlong;
+};
+
+// STEP 0: per segment local max m and sum of exp(x - m); att <- exp(x - m)
+// STEP 1: att *= factor[segment]
+// STEP 2: per segment sum of att * dal
+// STEP 3: dal <- att (dal - t[segment]) LeakyReLU'(x); per segment sum of those
+template <int STEP>
+__global__ __launch_bounds__(kBlock) void k_gat_segments(const GatRows g, const GatSegs q,
+                                                         float* __restrict__ att, float* __restrict__ dal,
+                                                         float* __restrict__ stat, const float* __restrict__ factor)
+{
+    const int t = threadIdx.x % kWave;
+    const int64_t sgi = (int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;
+    if (sgi >= q.nsegs) return;
+    const int32_t row = q.seg_row[sgi];
+    const int64_t eb = q.seg_begin[sgi], ee = eb + q.seg_len[sgi];
+    const float sd = g.sdst_own[row];
+    if (STEP == 0) {
+        float x[kPerLane];
+        float m = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < kPerLane; ++i) {
+            const int64_t e = eb + t + (int64_t)i * kWave;
+            x[i] = e < ee ? lrelu(g.ssrc(g.col[e]) + sd) : -INFINITY;
+            m = fmaxf(m, x[i]);
+        }
+        m = wave_max(m);
+        float sum = 0.f;
+#pragma unroll
+        for (int i = 0; i < kPerLane; ++i) {
+            const int64_t e = eb + t + (int64_t)i * kWave;
+            const float ex = expf(x[i] - m);
+            if (e < ee) att[e - g.e0] = ex;
+            sum += ex;
+        }
+        sum = wave_sum(sum);
+        if (t == 0) {
+            stat[2 * sgi] = m;
+            stat[2 * sgi + 1] = sum;
+        }
+    } else if (STEP == 1) {
+        const float f = factor[sgi];
+        for (int64_t e = eb + t; e < ee; e += kWave) att[e - g.e0] *= f;
+    } else if (STEP == 2) {
+        float tv = 0.f;
+        for (int64_t e = eb + t; e < ee; e += kWave) tv += att[e - g.e0] * dal[e - g.e0];
+        tv = wave_sum(tv);
+        if (t == 0) stat[sgi] = tv;
     } else {
-        const int64_t item = (int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;
-        if (item >= g.nranges) return;
-        const int32_t r1 = g.range_rows[item + 1];
-        for (int32_t row = g.range_rows[item]; row < r1; ++row) {
-            if (g.rp[row + 1] - g.rp[row] > kSpmmSegment) continue;     // long row: its own workgroup
-            if (MODE == 0) att_row<false>(g, row, att, sm);
-            else bwd_row<false>(g, row, att, dal, gs_dst_own, sm);
+        const float tv = factor[sgi];
+        float ds = 0.f;
+#pragma unroll
+        for (int i = 0; i < kPerLane; ++i) {
+            const int64_t e = eb + t + (int64_t)i * kWave;
+            if (e < ee) {
+                const float x = g.ssrc(g.col[e]) + sd;
+                const float dp = att[e - g.e0] * (dal[e - g.e0] - tv) * (x > 0.f ? 1.f : kSlope);
+                dal[e - g.e0] = dp;
+                ds += dp;
+            }
+        }
+        ds = wave_sum(ds);
+        if (t == 0) stat[sgi] = ds;
+    }
+}
+
+// One wavefront per long row, its segments in ascending order.
+// STEP 0: from (m, sum) per segment: factor[segment] = exp(m_seg - M) / S
+// STEP 2: factor[segment] = sum of the row's stat (the row's t)
+// STEP 3: gs_dst_own[row] = sum of the row's stat
+template <int STEP>
+__global__ __launch_bounds__(kBlock) void k_gat_combine(const GatSegs q, const float* __restrict__ stat,
+                                                        float* __restrict__ factor, float* __restrict__ gs_dst_own)
+{
+    const int t = threadIdx.x % kWave;
+    const int64_t i = (int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;
+    if (i >= q.nlong) return;
+    const int32_t first = q.long_first[i], ns = q.long_nseg[i];
+    if (STEP == 0) {
+        float M = -INFINITY;
+        for (int32_t j = t; j < ns; j += kWave) M = fmaxf(M, stat[2 * (int64_t)(first + j)]);
+        M = wave_max(M);
+        float S = 0.f;
+        for (int32_t j = t; j < ns; j += kWave)
+            S += stat[2 * (int64_t)(first + j) + 1] * expf(stat[2 * (int64_t)(first + j)] - M);
+        S = wave_sum(S);
+        const float inv = 1.f / S;
+        for (int32_t j = t; j < ns; j += kWave) factor[first + j] = expf(stat[2 * (int64_t)(first + j)] - M) * inv;
+    } else {
+        float v = 0.f;
+        for (int32_t j = t; j < ns; j += kWave) v += stat[first + j];
+        v = wave_sum(v);
+        if (STEP == 2) {
+            for (int32_t j = t; j < ns; j += kWave) factor[first + j] = v;
+        } else if (t == 0) {
+            gs_dst_own[q.long_row[i]] = v;
         }
     }
 }
@@ -183,10 +313,28 @@ __device__ inline void trow(const GatTRows& g, int32_t i, const float* __restric
     const int t = BLOCK ? threadIdx.x : threadIdx.x % kWave;
     const int64_t eb = g.trp[i], ee = g.trp[i + 1];
     float s = 0.f;
-    for (int64_t e = eb + t; e < ee; e += T) {
-        const int32_t fe = g.tperm[e];
-        tw_att[e - g.e0] = att[fe];
-        if (dpre) s += dpre[fe];
+    constexpr int U = 4;
+    for (int64_t e = eb + t; e < ee; e += (int64_t)T * U) {
+        int32_t fe[U];
+        float av[U], dv[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t eu = e + (int64_t)u * T;
+            fe[u] = g.tperm[eu < ee ? eu : ee - 1];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            av[u] = att[fe[u]];
+            dv[u] = dpre ? dpre[fe[u]] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t eu = e + (int64_t)u * T;
+            if (eu < ee) {
+                tw_att[eu - g.e0] = av[u];
+                s += dv[u];
+            }
+        }
     }
     if (!dpre) return;
     s = red_sum<BLOCK>(s, sm);
@@ -206,12 +354,30 @@ __global__ __launch_bounds__(kBlock) void k_gat_trows(const GatTRows g, const fl
         if (i >= g.nlong) return;
         trow<true>(g, g.long_row[i], att, dpre, tw_att, gs_src, sm);
     } else {
+        // transposed rows are short (a source feeds about ten destinations of a partition): a
+        // group of 16 lanes takes a row, four rows of the item at a time
+        constexpr int GW = 16;
+        const int lane = threadIdx.x % kWave, gl = lane % GW, grp = lane / GW;
         const int64_t item = (int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;
         if (item >= g.nranges) return;
         const int32_t r1 = g.range_rows[item + 1];
-        for (int32_t i = g.range_rows[item]; i < r1; ++i) {
-            if (g.trp[i + 1] - g.trp[i] > kSpmmSegment) continue;
-            trow<false>(g, i, att, dpre, tw_att, gs_src, sm);
+        for (int32_t i = g.range_rows[item] + grp; i < r1; i += kWave / GW) {
+            const int64_t eb = g.trp[i], ee = g.trp[i + 1];
+            if (ee - eb > kSpmmSegment) continue;
+            float sum = 0.f;
+            for (int64_t e = eb + gl; e < ee; e += GW) {
+                const int32_t fe = g.tperm[e];
+                tw_att[e - g.e0] = att[fe];
+                if (dpre) sum += dpre[fe];
+            }
+            if (dpre) {
+#pragma unroll
+                for (int m = 1; m < GW; m <<= 1) sum += __shfl_xor(sum, m, kWave);
+                if (gl == 0) {
+                    const int64_t r = i < g.n_own ? g.base_row + i : (int64_t)g.bnd[i - g.n_own];
+                    gs_src[r] += sum;
+                }
+            }
         }
     }
 }
@@ -345,26 +511,53 @@ static GatRows make_rows(const GatRowsHost& h)
     return g;
 }
 
-void launch_gat_attention(const GatRowsHost& h, float* att, hipStream_t s)
+static GatSegs make_segs(const GatRowsHost& h)
 {
-    const GatRows g = make_rows(h);
-    if (g.nranges > 0)
-        hipLaunchKernelGGL((k_gat_rows<0, false>), dim3((unsigned)((g.nranges + 3) / 4)), dim3(kBlock), 0, s, g,
-                           att, (float*)nullptr, (float*)nullptr);
-    if (g.nlong > 0)
-        hipLaunchKernelGGL((k_gat_rows<0, true>), dim3((unsigned)g.nlong), dim3(kBlock), 0, s, g, att,
-                           (float*)nullptr, (float*)nullptr);
+    GatSegs q;
+    q.seg_row = h.items.seg_row; q.seg_begin = h.items.seg_begin; q.seg_len = h.items.seg_len;
+    q.nsegs = h.items.nsegs;
+    q.long_row = h.items.long_row; q.long_first = h.items.long_first; q.long_nseg = h.items.long_nseg;
+    q.nlong = h.items.nlong;
+    return q;
 }
 
-void launch_gat_bwd_scalars(const GatRowsHost& h, const float* att, float* dal, float* gs_dst_own, hipStream_t s)
+// `segwork`: 3 floats per segment of the partition's long rows
+void launch_gat_attention(const GatRowsHost& h, float* att, float* segwork, hipStream_t s)
 {
     const GatRows g = make_rows(h);
     if (g.nranges > 0)
-        hipLaunchKernelGGL((k_gat_rows<1, false>), dim3((unsigned)((g.nranges + 3) / 4)), dim3(kBlock), 0, s, g,
+        hipLaunchKernelGGL((k_gat_rows<0>), dim3((unsigned)((g.nranges + 3) / 4)), dim3(kBlock), 0, s, g,
+                           att, (float*)nullptr, (float*)nullptr);
+    const GatSegs q = make_segs(h);
+    if (q.nsegs > 0 && q.nlong > 0) {
+        float* stat = segwork;
+        float* factor = segwork + 2 * q.nsegs;
+        const dim3 gs((unsigned)((q.nsegs + 3) / 4)), gl((unsigned)((q.nlong + 3) / 4)), b(kBlock);
+        hipLaunchKernelGGL((k_gat_segments<0>), gs, b, 0, s, g, q, att, (float*)nullptr, stat, (const float*)nullptr);
+        hipLaunchKernelGGL((k_gat_combine<0>), gl, b, 0, s, q, (const float*)stat, factor, (float*)nullptr);
+        hipLaunchKernelGGL((k_gat_segments<1>), gs, b, 0, s, g, q, att, (float*)nullptr, (float*)nullptr,
+                           (const float*)factor);
+    }
+}
+
+void launch_gat_bwd_scalars(const GatRowsHost& h, const float* att, float* dal, float* gs_dst_own,
+                            float* segwork, hipStream_t s)
+{
+    const GatRows g = make_rows(h);
+    if (g.nranges > 0)
+        hipLaunchKernelGGL((k_gat_rows<1>), dim3((unsigned)((g.nranges + 3) / 4)), dim3(kBlock), 0, s, g,
                            const_cast<float*>(att), dal, gs_dst_own);
-    if (g.nlong > 0)
-        hipLaunchKernelGGL((k_gat_rows<1, true>), dim3((unsigned)g.nlong), dim3(kBlock), 0, s, g,
-                           const_cast<float*>(att), dal, gs_dst_own);
+    const GatSegs q = make_segs(h);
+    if (q.nsegs > 0 && q.nlong > 0) {
+        float* stat = segwork;
+        float* factor = segwork + 2 * q.nsegs;
+        float* a = const_cast<float*>(att);
+        const dim3 gs((unsigned)((q.nsegs + 3) / 4)), gl((unsigned)((q.nlong + 3) / 4)), b(kBlock);
+        hipLaunchKernelGGL((k_gat_segments<2>), gs, b, 0, s, g, q, a, dal, stat, (const float*)nullptr);
+        hipLaunchKernelGGL((k_gat_combine<2>), gl, b, 0, s, q, (const float*)stat, factor, (float*)nullptr);
+        hipLaunchKernelGGL((k_gat_segments<3>), gs, b, 0, s, g, q, a, dal, stat, (const float*)factor);
+        hipLaunchKernelGGL((k_gat_combine<3>), gl, b, 0, s, q, (const float*)stat, (float*)nullptr, gs_dst_own);
+    }
 }
 
 void launch_gat_transposed(const int64_t* trp, const int32_t* tperm, int64_t e0, int64_t n_own,

@@ -104,6 +104,10 @@ CONFIGS = {
     "mid": dict(n=2_400_000, m_draw=70_500_000, seed=2, symmetric=True, self_loops=False,
                 model="sage", dims=(100, 256, 256, 47), dtype="f32", k=16, part="switching",
                 train_frac=0.1),
+    # the same graph and widths with graph-attention layers (the paper's second model family)
+    "mid_gat": dict(n=2_400_000, m_draw=70_500_000, seed=2, symmetric=True, self_loops=False,
+                    model="gat", dims=(100, 256, 256, 47), dtype="f32", k=16, part="switching",
+                    train_frac=0.1),
     # half of papers100M's shape: 50M nodes, ~800M directed edges, 3-layer GCN
     "large": dict(n=50_000_000, m_draw=830_000_000, seed=3, symmetric=False, self_loops=True,
                   model="gcn", dims=(128, 128, 128, 172), dtype="f32", k=64, part="lp",

@@ -39,6 +39,17 @@ def glorot_weights(dims, seed: int, *, sage: bool, bias_scale: float = 0.0):
     return out
 
 
+def attention_vectors(weights, seed: int, scale: float = 0.5):
+    """Adds the two attention vectors of a graph-attention layer (``a_src``, ``a_dst``, each
+    ``[d_out]``, ``N(0, scale^2 / d_out)`` so that scores stay O(1)) to every layer dict."""
+    rng = np.random.default_rng([seed, 0x6A7])
+    for layer in weights:
+        dout = layer["W"].shape[1]
+        layer["a_src"] = (rng.standard_normal(dout) * scale / np.sqrt(dout)).astype(np.float32)
+        layer["a_dst"] = (rng.standard_normal(dout) * scale / np.sqrt(dout)).astype(np.float32)
+    return weights
+
+
 def to_bf16_grid(x: np.ndarray) -> np.ndarray:
     """Round float32 values to the nearest bfloat16 (ties to even), returned as float32."""
     u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
