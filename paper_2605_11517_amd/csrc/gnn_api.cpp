@@ -139,6 +139,7 @@ void compute_workspace(gnn_ctx* c)
     if (hp > 0) {
         w.h = take(M.n * hp);
         w.gh = take(M.n * hp);
+        w.wpad = take(2 * din * hp);
     }
     if (c->model == GNN_GAT) {
         w.ssrc = take(M.n);
@@ -394,6 +395,31 @@ static int32_t all_done(const std::vector<uint8_t>& flags, int32_t layer, int32_
     return cnt;
 }
 
+// Rows of W (which = 0) or W_s (which = 1) of a transform-first layer padded to the layer's
+// padded width, so that every operand of its contractions has 16-byte rows; the weights
+// themselves when no padding is needed.
+struct PaddedW {
+    const float* p;
+    int32_t ld;
+};
+static PaddedW padded_weight(gnn_ctx* c, int32_t layer, int which)
+{
+    const int32_t din = c->dims[(size_t)layer - 1], dout = c->dims[(size_t)layer], dp = c->padded(layer);
+    const float* w = (const float*)c->w[(size_t)3 * (layer - 1) + which];
+    if (dp == dout) return {w, dout};
+    return {(const float*)(c->scratch + c->ws.wpad) + (int64_t)which * din * dp, dp};
+}
+static void refresh_padded_weights(gnn_ctx* c, int32_t layer, hipStream_t s)
+{
+    const int32_t din = c->dims[(size_t)layer - 1], dout = c->dims[(size_t)layer], dp = c->padded(layer);
+    if (dp == dout) return;
+    Timed t(c, s, GNN_K_OTHER);
+    float* base = (float*)(c->scratch + c->ws.wpad);
+    launch_pad_rows(base, (const float*)c->w[(size_t)3 * (layer - 1)], din, dout, dp, s);
+    if (c->model == GNN_SAGE_MEAN)
+        launch_pad_rows(base + (int64_t)din * dp, (const float*)c->w[(size_t)3 * (layer - 1) + 1], din, dout, dp, s);
+}
+
 // Transform-first layer, forward of partition p after H = A^{l-1} W exists for every vertex:
 // Z = S_p [H_own ; staging], A_p^l = act(Z (+ A_p^{l-1} W_s) + b).
 static void xf_aggregate_fwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
@@ -405,10 +431,11 @@ static void xf_aggregate_fwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s
     const float* rscale = c->D.rscale ? c->D.rscale + r0 : nullptr;
     float* Z = (float*)(c->scratch + c->ws.z);
     float* segpart = (float*)(c->scratch + c->ws.segpart);
-    const float* H = (const float*)(c->scratch + c->ws.h) + r0 * dp;
+    const bool b16 = c->bf16();        // H and staging hold bfloat16 rows then; Z is fp32 either way
+    const char* H = c->scratch + c->ws.h + r0 * dp * c->es();
     {
         Timed t(c, s, GNN_K_SPMM);
-        launch_spmm(c->D.rp + r0, c->D.lcol, c->D.ew, rscale, H, np, c->staging, Z, np, dp, 0, 0, items,
+        launch_spmm(c->D.rp + r0, c->D.lcol, c->D.ew, rscale, H, np, c->staging, Z, np, dp, b16 ? 1 : 0, 0, items,
                     segpart, 1, SpmmScatter{}, s);
     }
     if (items.nlong > 0) {
@@ -419,10 +446,19 @@ static void xf_aggregate_fwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s
     const float* bias = c->has_bias ? (const float*)c->w[(size_t)3 * (layer - 1) + 2] : nullptr;
     const int relu = layer < c->L ? 1 : 0;
     Timed t(c, s, GNN_K_GEMM_FWD);
-    if (c->model == GNN_SAGE_MEAN) {
+    if (c->model == GNN_SAGE_MEAN && b16) {
+        GemmSegBf16 seg;
+        seg.a = c->layer_input(layer, r0); seg.lda = din;
+        seg.b = c->w[(size_t)3 * (layer - 1) + 1]; seg.ldb = dout; seg.k = din;
+        GemmEpilogue ep;
+        ep.bias = bias;
+        launch_gemm_bf16_nn(&seg, 1, out, 0, dout, np, dout, ep, s);
+        launch_add_padded(out, Z, np, dout, dp, nullptr, 1, relu, s);
+    } else if (c->model == GNN_SAGE_MEAN) {
+        const PaddedW ws = padded_weight(c, layer, 1);
         GemmSeg seg;
         seg.a = (const float*)c->layer_input(layer, r0); seg.lda = din;
-        seg.b = (const float*)c->w[(size_t)3 * (layer - 1) + 1]; seg.ldb = dout; seg.k = din;
+        seg.b = ws.p; seg.ldb = ws.ld; seg.k = din;
         GemmEpilogue ep;
         ep.bias = bias;
         launch_gemm_nn(&seg, 1, out, dout, np, dout, ep, s);
@@ -451,6 +487,40 @@ static void xf_aggregate_bwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s
     float* colpart = (float*)(c->scratch + c->ws.colpart);
     const float* g_own = c->gact[(size_t)layer - 1] + r0 * dout;
     const float drop_scale = c->dropout_p > 0.f ? 1.f / (1.f - c->dropout_p) : 1.f;
+    if (c->bf16()) {
+        // output layer with bfloat16 storage (dp == dout): dY as bfloat16, the rest as below
+        {
+            Timed t(c, s, GNN_K_ACT_BWD);
+            launch_act_bwd_bf16(g_own, nullptr, dYbuf, np, dout, gb, colpart, 1.f, s);
+        }
+        if (c->model == GNN_SAGE_MEAN) {
+            {
+                Timed t(c, s, GNN_K_GEMM_DW);
+                launch_gemm_bf16_tn(c->layer_input(layer, r0), din, dYbuf, dout, c->gw[(size_t)3 * (layer - 1) + 1],
+                                    dout, din, dout, np, (float*)(c->scratch + c->ws.partial), s);
+            }
+            if (layer >= 2)
+                compute_bwd_self(c, layer, p, (const char*)dYbuf, c->gact[(size_t)layer - 2] + r0 * din, s);
+        }
+        const int64_t t0b = M.toff[(size_t)p];
+        const SpmmItems itb = plan_items(M.plan_bwd, c->D.bwd, p);
+        float* segb = (float*)(c->scratch + c->ws.segpart);
+        SpmmScatter scb;
+        scb.n_own = np;
+        scb.base_row = r0;
+        scb.idx = c->D.bnd + M.boff[(size_t)p];
+        float* gHb = (float*)(c->scratch + c->ws.gh);
+        {
+            Timed t(c, s, GNN_K_SPMM_T);
+            launch_spmm(c->D.trp + t0b, c->D.tcol, c->D.tw, nullptr, dYbuf, np, nullptr, gHb, np + nb, dp, 1, 0, itb,
+                        segb, 0, scb, s);
+        }
+        if (itb.nlong > 0) {
+            Timed t(c, s, GNN_K_SPMM_REDUCE);
+            launch_spmm_reduce(nullptr, gHb, dp, 0, itb, segb, scb, s);
+        }
+        return;
+    }
     const float* dY = g_own;
     {
         Timed t(c, s, GNN_K_ACT_BWD);
@@ -463,20 +533,28 @@ static void xf_aggregate_bwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s
         }
     }
     const float* in_own = (const float*)c->layer_input(layer, r0);
-    if (c->model == GNN_SAGE_MEAN) {
-        {
-            Timed t(c, s, GNN_K_GEMM_DW);
-            launch_gemm_tn(in_own, din, dY, dout, c->gw[(size_t)3 * (layer - 1) + 1], dout, din, dout, np,
-                           (float*)(c->scratch + c->ws.partial), s);
-        }
-        if (layer >= 2) compute_bwd_self(c, layer, p, (const char*)dY, c->gact[(size_t)layer - 2] + r0 * din, s);
-    }
+    // dY with rows padded to whole vectors (zeros in the padding): the operand of everything below
     const float* dYp = dY;
     if (dp != dout) {
         Timed t(c, s, GNN_K_OTHER);
         float* pad = (float*)(c->scratch + c->ws.dz);
         launch_pad_rows(pad, dY, np, dout, dp, s);
         dYp = pad;
+    }
+    if (c->model == GNN_SAGE_MEAN) {
+        {
+            Timed t(c, s, GNN_K_GEMM_DW);
+            launch_gemm_tn(in_own, din, dYp, dp, c->gw[(size_t)3 * (layer - 1) + 1], dout, din, dout, np,
+                           (float*)(c->scratch + c->ws.partial), s);
+        }
+        if (layer >= 2) {
+            // self term: grad A^{l-1}_own += dY W_s^T, contracted over the padded width
+            const PaddedW ws = padded_weight(c, layer, 1);
+            Timed t(c, s, GNN_K_GEMM_DZ);
+            GemmEpilogue ep;
+            ep.accumulate = 1;
+            launch_gemm_nt(dYp, dp, ws.p, ws.ld, c->gact[(size_t)layer - 2] + r0 * din, din, np, din, dp, ep, s);
+        }
     }
     const int64_t t0 = M.toff[(size_t)p];
     const SpmmItems items = plan_items(M.plan_bwd, c->D.bwd, p);
@@ -725,7 +803,7 @@ gnn_status gnn_gather_boundary(gnn_ctx* c, int32_t layer, int32_t p, void* strea
             return check_launch(c, "gnn_gather_boundary");
         }
         Timed t(c, s, GNN_K_GATHER);
-        launch_gather_rows(c->scratch + c->ws.h, c->D.bnd + b0, c->staging, nb, (int64_t)c->padded(layer) * 4, s);
+        launch_gather_rows(c->scratch + c->ws.h, c->D.bnd + b0, c->staging, nb, (int64_t)c->padded(layer) * c->es(), s);
     } else {
         const int64_t row_bytes = (int64_t)c->dims[(size_t)layer - 1] * c->es();
         Timed t(c, s, GNN_K_GATHER);
@@ -796,18 +874,26 @@ gnn_status gnn_layer_transform_fwd(gnn_ctx* c, int32_t layer, int32_t p, void* s
     }
     const int64_t r0 = M.off[(size_t)p], np = M.off[(size_t)p + 1] - r0;
     const int32_t din = c->dims[(size_t)layer - 1], dout = c->dims[(size_t)layer], dp = c->padded(layer);
-    float* H = (float*)(c->scratch + c->ws.h) + r0 * dp;
-    if (dp != dout) {
-        // columns dout..dp of H are read by the aggregation as part of whole vectors
-        Timed t(c, s, GNN_K_OTHER);
-        launch_fill_zero(H, np * (int64_t)dp * 4, s);
+    if (c->bf16()) {
+        // bfloat16 storage (dp == dout): H in bfloat16
+        Timed t(c, s, GNN_K_GEMM_FWD);
+        GemmSegBf16 seg;
+        seg.a = c->layer_input(layer, r0); seg.lda = din;
+        seg.b = c->w[(size_t)3 * (layer - 1)]; seg.ldb = dout; seg.k = din;
+        launch_gemm_bf16_nn(&seg, 1, c->scratch + c->ws.h + r0 * dp * 2, 1, dp, np, dout, GemmEpilogue{}, s);
+        c->xf_fwd_done[(size_t)(layer - 1) * (size_t)M.k + (size_t)p] = 1;
+        return check_launch(c, "gnn_layer_transform_fwd");
     }
+    float* H = (float*)(c->scratch + c->ws.h) + r0 * dp;
+    refresh_padded_weights(c, layer, s);
     {
+        // all dp columns are computed: the padding columns of W are zero, so are those of H
+        const PaddedW w = padded_weight(c, layer, 0);
         Timed t(c, s, GNN_K_GEMM_FWD);
         GemmSeg seg;
         seg.a = (const float*)c->layer_input(layer, r0); seg.lda = din;
-        seg.b = (const float*)c->w[(size_t)3 * (layer - 1)]; seg.ldb = dout; seg.k = din;
-        launch_gemm_nn(&seg, 1, H, dp, np, dout, GemmEpilogue{}, s);
+        seg.b = w.p; seg.ldb = w.ld; seg.k = din;
+        launch_gemm_nn(&seg, 1, H, dp, np, w.ld == dp ? dp : dout, GemmEpilogue{}, s);
     }
     c->xf_fwd_done[(size_t)(layer - 1) * (size_t)M.k + (size_t)p] = 1;
     return check_launch(c, "gnn_layer_transform_fwd");
@@ -831,6 +917,28 @@ gnn_status gnn_layer_transform_bwd(gnn_ctx* c, int32_t layer, int32_t p, void* s
     const int64_t r0 = M.off[(size_t)p], np = M.off[(size_t)p + 1] - r0;
     const int32_t din = c->dims[(size_t)layer - 1], dout = c->dims[(size_t)layer], dp = c->padded(layer);
     const float* gH = (const float*)(c->scratch + c->ws.gh) + r0 * dp;
+    if (c->bf16()) {
+        // the contractions take bfloat16 operands: grad H of this partition is rounded once
+        char* gHb = c->scratch + c->ws.dz;
+        {
+            Timed t(c, s, GNN_K_OTHER);
+            launch_to_bf16(gH, gHb, np * (int64_t)dp, s);
+        }
+        {
+            Timed t(c, s, GNN_K_GEMM_DW);
+            launch_gemm_bf16_tn(c->layer_input(layer, r0), din, gHb, dp, c->gw[(size_t)3 * (layer - 1)], dout, din,
+                                dout, np, (float*)(c->scratch + c->ws.partial), s);
+        }
+        if (layer >= 2) {
+            Timed t(c, s, GNN_K_GEMM_DZ);
+            GemmEpilogue ep;
+            ep.accumulate = 1;
+            launch_gemm_bf16_nt(gHb, dp, c->w[(size_t)3 * (layer - 1)], dout, c->gact[(size_t)layer - 2] + r0 * din, 0,
+                                din, np, din, dout, ep, s);
+        }
+        c->xf_bwd_done[(size_t)(layer - 1) * (size_t)M.k + (size_t)p] = 1;
+        return check_launch(c, "gnn_layer_transform_bwd");
+    }
     const float* in_own = (const float*)c->layer_input(layer, r0);
     {
         Timed t(c, s, GNN_K_GEMM_DW);
@@ -838,11 +946,11 @@ gnn_status gnn_layer_transform_bwd(gnn_ctx* c, int32_t layer, int32_t p, void* s
                        (float*)(c->scratch + c->ws.partial), s);
     }
     if (layer >= 2) {
+        const PaddedW w = padded_weight(c, layer, 0);
         Timed t(c, s, GNN_K_GEMM_DZ);
         GemmEpilogue ep;
         ep.accumulate = 1;
-        launch_gemm_nt(gH, dp, (const float*)c->w[(size_t)3 * (layer - 1)], dout,
-                       c->gact[(size_t)layer - 2] + r0 * din, din, np, din, dout, ep, s);
+        launch_gemm_nt(gH, dp, w.p, w.ld, c->gact[(size_t)layer - 2] + r0 * din, din, np, din, dp, ep, s);
     }
     c->xf_bwd_done[(size_t)(layer - 1) * (size_t)M.k + (size_t)p] = 1;
     return check_launch(c, "gnn_layer_transform_bwd");
@@ -906,10 +1014,13 @@ gnn_status gnn_layer_bwd(gnn_ctx* c, int32_t layer, int32_t p, void* stream)
     if (c->transform_first(layer)) {
         // no regather and no recompute: the layer aggregated H, whose gradient is accumulated here
         if (c->bwd_done[(size_t)layer] == 0) {
-            Timed t(c, s, GNN_K_OTHER);
-            launch_fill_zero(c->scratch + c->ws.gh, c->M.n * (int64_t)c->padded(layer) * 4, s);
-            if (layer >= 2)
-                launch_fill_zero(c->gact[(size_t)layer - 2], c->M.n * (int64_t)c->dims[(size_t)layer - 1] * 4, s);
+            {
+                Timed t(c, s, GNN_K_OTHER);
+                launch_fill_zero(c->scratch + c->ws.gh, c->M.n * (int64_t)c->padded(layer) * 4, s);
+                if (layer >= 2)
+                    launch_fill_zero(c->gact[(size_t)layer - 2], c->M.n * (int64_t)c->dims[(size_t)layer - 1] * 4, s);
+            }
+            refresh_padded_weights(c, layer, s);
             for (int32_t q = 0; q < c->M.k; ++q) c->xf_bwd_done[(size_t)(layer - 1) * (size_t)c->M.k + (size_t)q] = 0;
         }
         xf_aggregate_bwd(c, layer, p, s);

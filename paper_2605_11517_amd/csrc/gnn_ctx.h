@@ -39,6 +39,7 @@ struct Workspace {  // byte offsets into `scratch`
     int64_t z = 0, dy = 0, dz = 0, dga = 0, partial = 0, colpart = 0, losspart = 0, scalars = 0,
             segpart = 0;
     int64_t h = 0, gh = 0;     // transform-first layers: H = A W and its gradient, n x padded width
+    int64_t wpad = 0;          // and copies of W, W_s with rows padded to that width (2 x d_in x padded)
     // graph attention: per-vertex scores and their gradients, staged boundary scores, per-entry
     // attention weights, edge-wise products, attention weights in transposed order
     int64_t ssrc = 0, sdst = 0, gssrc = 0, gsdst = 0, bs = 0, att = 0, dal = 0, twatt = 0;
@@ -79,8 +80,10 @@ struct gnn_ctx {
     bool transform_first(int32_t layer) const
     {
         if (model == GNN_GAT) return true;       // attention scores are taken from H = A W
-        return order_mode == 1 && !streaming() && !bf16() &&
-               dims[(size_t)layer] < dims[(size_t)layer - 1];
+        if (order_mode != 1 || streaming() || dims[(size_t)layer] >= dims[(size_t)layer - 1]) return false;
+        // bfloat16 storage: only the output layer (its result is fp32 anyway), and only when its
+        // rows are whole 16-byte vectors
+        return !bf16() || (layer == L && dims[(size_t)layer] % 8 == 0);
     }
     // width of H rows: d_layer rounded up to whole 16-byte vectors
     int32_t padded(int32_t layer) const { return (dims[(size_t)layer] + 3) / 4 * 4; }

@@ -342,8 +342,9 @@ void launch_gemm(const GemmArgs& g, int splits, hipStream_t s)
         va = va && aligned16(g.a[i].p) && g.a[i].ld % 4 == 0 && (!A_KFAST || g.kseg[i] % 4 == 0);
         vb = vb && aligned16(g.b[i].p) && g.b[i].ld % 4 == 0 && (!B_KFAST || g.kseg[i] % 4 == 0);
     }
-    if (!A_KFAST) va = va && g.m % 4 == 0;
-    if (!B_KFAST) vb = vb && g.n % 4 == 0;
+    // (an operand whose m or n index is the contiguous one needs no such condition: its rows are
+    // ld >= m (or n) floats long with ld a multiple of 4, so the last vector of a row stays inside
+    // the row; what it reads past m (or n) only reaches columns of C that are never stored)
     const bool big_m = g.m > 64, big_n = g.n > 64;
 #define GNN_GEMM(BM, BN, VA, VB)                                                                \
     hipLaunchKernelGGL((k_gemm<BM, BN, A_KFAST, B_KFAST, VA, VB>),                              \

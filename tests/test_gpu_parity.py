@@ -222,10 +222,11 @@ BF16_CASES = [
 ]
 
 
+@pytest.mark.parametrize("order", ["aggregate", "auto"])
 @pytest.mark.parametrize("case", BF16_CASES, ids=lambda c: "%s-%s" % (c[0], "x".join(map(str, c[1]))))
-def test_bf16_storage_matches_oracle(case):
+def test_bf16_storage_matches_oracle(case, order):
     model, dims, n, m_draw, sym, k, mode = case
-    say("case bf16 %s" % (case,))
+    say("case bf16 %s layer order %s" % (case, order))
     from paper_2605_11517_amd import Session
     from synth import to_bf16_grid
     rowptr, colidx = small_graph(n, m_draw, seed=41, symmetric=sym, self_loops=False)
@@ -237,7 +238,11 @@ def test_bf16_storage_matches_oracle(case):
         layer["W"] = to_bf16_grid(layer["W"])
         if layer["Ws"] is not None:
             layer["Ws"] = to_bf16_grid(layer["Ws"])
-    s = Session(model, dims, rowptr, colidx, k, mode, 3, X, w, y, m, dtype="bf16")
+    s = Session(model, dims, rowptr, colidx, k, mode, 3, X, w, y, m, dtype="bf16", layer_order=order)
+    L = len(dims) - 1
+    # with bfloat16 storage only an output layer of whole 16-byte rows may transform first
+    want = [order == "auto" and l == L and dims[l] < dims[l - 1] and dims[l] % 8 == 0 for l in range(1, L + 1)]
+    assert [s.ctx.layer_is_transform_first(l) for l in range(1, L + 1)] == want
     loss = s.epoch()
     got = s.results()
     fwd = og.forward(model, rowptr, colidx, dims, X, w)
