@@ -185,3 +185,44 @@ def test_partition_order_follows_shared_blocks():
     cfg, rp, ci = make_config("tiny")
     ctx.build_partitions(rp, ci, 4, "random", 1)
     assert list(ctx.get_schedule()) == [0, 1, 2, 3]
+
+
+def test_errors_of_the_training_order_and_attention_entry_points():
+    from paper_2605_11517_amd.binding import make_optimizer
+    rowptr, colidx = small_graph(30, 100, seed=1)
+    ctx = Context("sage", (8, 8, 4))
+    for p in (-0.1, 1.0, float("nan")):
+        with pytest.raises(GnnError) as e:
+            ctx.set_dropout(p, 0, 0)
+        assert e.value.status == 1
+    ctx.set_dropout(0.5, 1, 2)
+    with pytest.raises(GnnError) as e:
+        ctx._check(ctx.lib.gnn_set_layer_order(ctx.h, 7))
+    assert e.value.status == 1
+    ctx.set_layer_order("auto")
+    ctx.build_partitions(rowptr, colidx, 3, "random")
+    assert [ctx.layer_is_transform_first(l) for l in (1, 2)] == [False, True]
+    with pytest.raises(GnnError) as e:
+        ctx.layer_is_transform_first(3)
+    assert e.value.status == 1
+    # nothing is bound: the stepping entry points and the optimizer refuse, they do not touch a device
+    for call in (lambda: ctx.layer_transform_fwd(2, 0, None), lambda: ctx.layer_transform_bwd(2, 0, None),
+                 lambda: ctx.optimizer_step(make_optimizer("adam"), 1, None)):
+        with pytest.raises(GnnError) as e:
+            call()
+        assert e.value.status == 4
+    # graph attention: fp32 and the resident schedule only; schedule and boundary lists as for GCN
+    with pytest.raises(GnnError) as e:
+        Context("gat", (8, 8, 4), dtype=1)
+    assert e.value.status == 5
+    with pytest.raises(GnnError) as e:
+        Context("gat", (8, 8, 4), hbm_budget_bytes=1 << 30)
+    assert e.value.status == 5
+    gat = Context("gat", (8, 8, 4))
+    gcn = Context("gcn", (8, 8, 4))
+    for c in (gat, gcn):
+        c.build_partitions(rowptr, colidx, 3, "lp", seed=4)
+    assert gat.get_stats() == gcn.get_stats()            # same operator structure: A + I
+    for p in range(3):
+        assert np.array_equal(gat.get_boundary(p), gcn.get_boundary(p))
+    assert all(gat.layer_is_transform_first(l) for l in (1, 2))
