@@ -1,21 +1,26 @@
 // Streaming schedule: activations and their gradients live in pinned host memory, one block
-// per (layer, partition); HBM holds a cache of blocks at partition granularity.
+// per (layer, partition); a pool of HBM caches them.
 //
 // This is the one-GPU analogue of the paper's partition-wise cache (section on partition-wise
 // caching; overlap design in the appendix on I/O optimisations), with HBM in the role of the
 // host cache and pinned host memory in the role of storage:
-//   - for layer l only blocks of layer l-1 are cached, loaded when a partition depends on them
-//     and evicted whole blocks at a time.  The order in which blocks are needed is fixed by
-//     the partition dependencies (partition p touches its own block, then the owners of its
-//     boundary rows in ascending order), so the victim is the block whose next use lies
-//     furthest ahead; least-recently-used would evict exactly the block needed next whenever
-//     the partitions depend on more blocks than the cache holds;
+//   - the pool holds whole per-layer arrays while they fit ("layer-wise" caching: an array of k
+//     partition blocks, each block loaded or produced at most once) and falls back to a cache
+//     of single partition blocks for an array that does not fit (the paper's partition-wise
+//     eviction).  When room is needed the array of the lowest layer goes first: forward needs it
+//     no more and backward needs it last;
+//   - in the block cache a block is loaded when a partition depends on it and evicted whole.  The
+//     order in which blocks are needed is fixed by the partition dependencies (a partition
+//     touches its own block, then the owners of its boundary rows in ascending order), so the
+//     victim is the block whose next use lies furthest ahead; least-recently-used would evict
+//     exactly the block needed next whenever the partitions depend on more blocks than fit;
 //   - the boundary list of a partition is ordered by source partition, so the gather walks it
 //     one cached block at a time ("a single lookup per partition");
-//   - outputs A_p^l bypass the cache: they go from a transfer buffer straight to their host
-//     block;
-//   - the gradient of layer l-1 is a write-back cache of blocks: first touch zero-fills,
-//     eviction and the end of the layer write back;
+//   - outputs A_p^l bypass the cache on their way out: they are stored to their host block
+//     straight from where the kernel wrote them (a transfer buffer, or their block of a resident
+//     array, where the next layer then finds them without a load);
+//   - the gradient of layer l-1 is written back: first touch zero-fills, eviction and the end of
+//     the layer write back;
 //   - loads of the next partition's blocks are issued on a side stream while the current
 //     partition computes, stores on a second side stream.
 // The arithmetic per partition is the resident schedule's, kernel for kernel, so results are
@@ -24,6 +29,7 @@
 #include <climits>
 #include <cstdint>
 #include <cstring>
+#include <memory>
 
 #include "gnn_ctx.h"
 
@@ -45,30 +51,45 @@ struct Slot {
 struct BlockCache {
     char* pool = nullptr;
     int64_t pool_bytes = 0, slot_bytes = 0, row_bytes = 0;
-    std::vector<Slot> slots;        // events are created once for the largest slot count
+    std::vector<Slot> slots;
     int32_t nslots = 0;
     std::vector<int32_t> slot_of;   // partition -> slot or -1
     std::vector<uint8_t> touched;   // write-back cache: block exists (on host or in a slot)
-    char* host = nullptr;           // backing array of the current layer
+    char* host = nullptr;           // backing array
     bool writeback = false;
+    bool identity = false;          // a whole array: block p lives in slot p and is never evicted
     int32_t cur_t = 0;              // step (position in the partition order) whose accesses are being issued
     int64_t tick = 0;
-    int64_t loads = 0, hits = 0, writebacks = 0;
     char* ptr(int32_t s) const { return pool + (int64_t)s * slot_bytes; }
+    bool holds(int32_t part) const { return slot_of[(size_t)part] >= 0; }
+};
+
+enum ArrayKind { ARR_ACT = 0, ARR_GRAD = 1 };
+
+// A whole per-vertex array of one layer kept in the pool: (ARR_ACT, l) = A^l (l = 0: the
+// features), (ARR_GRAD, l) = grad A^l.
+struct Resident {
+    int kind = 0, layer = 0;
+    int64_t off = 0, bytes = 0;
+    BlockCache bc;
 };
 
 }  // namespace
 
 struct StreamEngine {
     hipStream_t h2d = nullptr, d2h = nullptr;
-    char* pool = nullptr;           // hbm_budget bytes, carved into the two caches per layer
+    char* pool = nullptr;
     int64_t pool_bytes = 0;
-    BlockCache actc, gradc;
+    std::vector<std::pair<int64_t, int64_t>> free_list;    // (offset, bytes), ascending, coalesced
+    std::vector<std::unique_ptr<Resident>> arrays;
+    BlockCache actc, gradc;         // block caches for arrays that are not resident
+    std::vector<Slot> spare;        // slots (with their events) of released arrays
     // next_dep[t * k + b] = first step t' >= t whose partition touches block b (k if none);
     // row k is all k.  Steps follow the order of HostMeta::sched.
     std::vector<int32_t> next_dep;
     int32_t k = 0;
     int64_t h2d_bytes = 0, d2h_bytes = 0;   // of the running epoch
+    int64_t loads[2] = {0, 0}, hits[2] = {0, 0}, writebacks = 0;
     char* io = nullptr;             // 6 transfer buffers
     int64_t io_bytes = 0;           // bytes of one buffer
     hipEvent_t out_ready[2]{}, out_done[2]{}, in_ready[2]{}, in_released[2]{};
@@ -88,30 +109,99 @@ namespace {
             return c->fail(GNN_EHIP, std::string(#call) + ": " + hipGetErrorString(e_));    \
     } while (0)
 
-gnn_status configure(gnn_ctx* c, BlockCache& bc, char* pool, int64_t pool_bytes, int64_t slot_bytes,
-                     int64_t row_bytes, char* host, bool writeback)
+inline int64_t round256(int64_t b) { return (std::max<int64_t>(b, 1) + 255) / 256 * 256; }
+
+// ---- pool regions ---------------------------------------------------------------------------
+int64_t pool_alloc(StreamEngine& E, int64_t bytes)
 {
-    slot_bytes = (slot_bytes + 255) / 256 * 256;
-    if (slot_bytes <= 0) slot_bytes = 256;
-    const int64_t n = pool_bytes / slot_bytes;
-    if (n < 2)
+    for (size_t i = 0; i < E.free_list.size(); ++i) {
+        auto& f = E.free_list[i];
+        if (f.second >= bytes) {
+            const int64_t off = f.first;
+            f.first += bytes;
+            f.second -= bytes;
+            if (f.second == 0) E.free_list.erase(E.free_list.begin() + (long)i);
+            return off;
+        }
+    }
+    return -1;
+}
+void pool_free(StreamEngine& E, int64_t off, int64_t bytes)
+{
+    auto it = E.free_list.begin();
+    while (it != E.free_list.end() && it->first < off) ++it;
+    it = E.free_list.insert(it, {off, bytes});
+    if (it + 1 != E.free_list.end() && it->first + it->second == (it + 1)->first) {
+        it->second += (it + 1)->second;
+        E.free_list.erase(it + 1);
+    }
+    if (it != E.free_list.begin() && (it - 1)->first + (it - 1)->second == it->first) {
+        (it - 1)->second += it->second;
+        E.free_list.erase(it);
+    }
+}
+std::pair<int64_t, int64_t> largest_free(const StreamEngine& E)
+{
+    std::pair<int64_t, int64_t> best{0, 0};
+    for (const auto& f : E.free_list)
+        if (f.second > best.second) best = f;
+    return best;
+}
+
+gnn_status new_slot(gnn_ctx* c, StreamEngine& E, Slot& out)
+{
+    if (!E.spare.empty()) {
+        out = E.spare.back();
+        E.spare.pop_back();
+    } else {
+        out = Slot{};
+        GNN_HIP(hipEventCreateWithFlags(&out.ready, hipEventDisableTiming));
+        GNN_HIP(hipEventCreateWithFlags(&out.released, hipEventDisableTiming));
+        GNN_HIP(hipEventCreateWithFlags(&out.flushed, hipEventDisableTiming));
+    }
+    out.part = -1;
+    out.dirty = out.pinned = false;
+    out.last_use = 0;
+    out.has_ready = out.has_released = out.has_flushed = false;
+    return GNN_OK;
+}
+
+// (Re)cuts a cache over `pool_bytes` at `pool` into slots of `slot_bytes`; contents are dropped.
+gnn_status configure(gnn_ctx* c, StreamEngine& E, BlockCache& bc, char* pool, int64_t pool_bytes,
+                     int64_t slot_bytes, int64_t row_bytes, char* host, bool writeback, bool identity)
+{
+    slot_bytes = round256(slot_bytes);
+    int64_t n = pool_bytes / slot_bytes;
+    if (n < 2 && !identity)
         return c->fail(GNN_ENOMEM, "hbm_budget_bytes is too small: a block cache needs room for two "
                                    "partition blocks of the widest layer");
+    n = std::min<int64_t>(n, (int64_t)E.k);          // one slot per partition is all that is useful
     bc.pool = pool;
     bc.pool_bytes = pool_bytes;
     bc.slot_bytes = slot_bytes;
     bc.row_bytes = row_bytes;
-    bc.nslots = (int32_t)std::min<int64_t>(n, (int64_t)bc.slots.size());
     bc.host = host;
     bc.writeback = writeback;
+    bc.identity = identity;
+    while ((int64_t)bc.slots.size() > n) {
+        E.spare.push_back(bc.slots.back());
+        bc.slots.pop_back();
+    }
+    while ((int64_t)bc.slots.size() < n) {
+        Slot sl;
+        gnn_status st = new_slot(c, E, sl);
+        if (st != GNN_OK) return st;
+        bc.slots.push_back(sl);
+    }
+    bc.nslots = (int32_t)n;
     for (Slot& s : bc.slots) {
         s.part = -1;
-        s.dirty = false;
-        s.pinned = false;
+        s.dirty = s.pinned = false;
         s.last_use = 0;
+        s.has_ready = s.has_released = s.has_flushed = false;
     }
-    std::fill(bc.slot_of.begin(), bc.slot_of.end(), -1);
-    std::fill(bc.touched.begin(), bc.touched.end(), 0);
+    bc.slot_of.assign((size_t)E.k, -1);
+    bc.touched.assign((size_t)E.k, 0);
     return GNN_OK;
 }
 
@@ -128,7 +218,7 @@ gnn_status write_back(gnn_ctx* c, StreamEngine& E, BlockCache& bc, int32_t s)
     GNN_HIP(hipEventRecord(sl.flushed, E.d2h));
     sl.has_flushed = true;
     sl.dirty = false;
-    ++bc.writebacks;
+    ++E.writebacks;
     E.d2h_bytes += np * bc.row_bytes;
     return GNN_OK;
 }
@@ -158,6 +248,7 @@ int64_t next_use(const StreamEngine& E, const std::vector<int32_t>& sched, int32
 int32_t pick_victim(const StreamEngine& E, const std::vector<int32_t>& sched, const BlockCache& bc,
                     int32_t part)
 {
+    if (bc.identity) return part;
     const int64_t now = access_pos(E.k, bc.cur_t, sched[(size_t)bc.cur_t], part);
     int32_t best = -1;
     int64_t best_next = -1;
@@ -182,9 +273,10 @@ gnn_status acquire(gnn_ctx* c, StreamEngine& E, BlockCache& bc, int32_t part, hi
                    bool wait, int32_t* slot_out)
 {
     const HostMeta& M = c->M;
+    const int kind = bc.writeback ? 1 : 0;
     int32_t s = bc.slot_of[(size_t)part];
     if (s >= 0) {
-        ++bc.hits;
+        ++E.hits[kind];
     } else {
         s = pick_victim(E, M.sched, bc, part);
         if (s < 0) {
@@ -214,7 +306,7 @@ gnn_status acquire(gnn_ctx* c, StreamEngine& E, BlockCache& bc, int32_t part, hi
                                        hipMemcpyHostToDevice, E.h2d));
             GNN_HIP(hipEventRecord(sl.ready, E.h2d));
             sl.has_ready = true;
-            ++bc.loads;
+            ++E.loads[kind];
             E.h2d_bytes += np * bc.row_bytes;
         }
         sl.part = part;
@@ -238,18 +330,18 @@ gnn_status mark_used(gnn_ctx* c, BlockCache& bc, int32_t s, hipStream_t compute,
     return GNN_OK;
 }
 
-// Gather of partition p's boundary rows from the cached blocks of layer l-1, one source
-// partition at a time.  Leaves the own block pinned and returns its slot.
-gnn_status gather_from_cache(gnn_ctx* c, StreamEngine& E, int32_t layer, int32_t t, hipStream_t s,
-                             int32_t* own_slot)
+// Gather of the boundary rows of the partition of step t from the cached blocks of layer l-1,
+// one source partition at a time.  Leaves the own block pinned and returns its slot.
+gnn_status gather_from_cache(gnn_ctx* c, StreamEngine& E, BlockCache& bc, int32_t layer, int32_t t,
+                             hipStream_t s, int32_t* own_slot)
 {
     const HostMeta& M = c->M;
     const int32_t k = M.k, p = M.sched[(size_t)t];
     const int64_t row_bytes = (int64_t)c->dims[(size_t)layer - 1] * c->es();
-    E.actc.cur_t = t;
-    gnn_status st = acquire(c, E, E.actc, p, s, true, own_slot);
+    bc.cur_t = t;
+    gnn_status st = acquire(c, E, bc, p, s, true, own_slot);
     if (st != GNN_OK) return st;
-    E.actc.slots[(size_t)*own_slot].pinned = true;
+    bc.slots[(size_t)*own_slot].pinned = true;
     const int64_t* run = M.brun.data() + (size_t)p * ((size_t)k + 1);
     const int64_t b0 = M.boff[(size_t)p];
     Timed timed(c, s, GNN_K_GATHER);
@@ -257,38 +349,151 @@ gnn_status gather_from_cache(gnn_ctx* c, StreamEngine& E, int32_t layer, int32_t
         const int64_t len = run[q + 1] - run[q];
         if (len <= 0) continue;
         int32_t sq;
-        if ((st = acquire(c, E, E.actc, q, s, true, &sq)) != GNN_OK) return st;
-        launch_gather_rows(E.actc.ptr(sq), c->D.bnd_local + b0 + run[q], c->staging + run[q] * row_bytes,
+        if ((st = acquire(c, E, bc, q, s, true, &sq)) != GNN_OK) return st;
+        launch_gather_rows(bc.ptr(sq), c->D.bnd_local + b0 + run[q], c->staging + run[q] * row_bytes,
                            len, row_bytes, s);
-        if ((st = mark_used(c, E.actc, sq, s, false)) != GNN_OK) return st;
+        if ((st = mark_used(c, bc, sq, s, false)) != GNN_OK) return st;
     }
     return GNN_OK;
 }
 
 // Issues loads for the blocks the partition of step t will need, as long as a slot can be
 // taken for them.
-gnn_status prefetch_for(gnn_ctx* c, StreamEngine& E, int32_t t, hipStream_t s)
+gnn_status prefetch_for(gnn_ctx* c, StreamEngine& E, BlockCache& bc, int32_t t, hipStream_t s)
 {
     const HostMeta& M = c->M;
     const int32_t k = M.k;
     if (t >= k) return GNN_OK;
     const int32_t p = M.sched[(size_t)t];
     const int64_t* run = M.brun.data() + (size_t)p * ((size_t)k + 1);
-    int32_t budget = E.actc.nslots - 1;      // never cycle the whole cache for a prefetch
+    int32_t budget = bc.nslots - 1;      // never cycle the whole cache for a prefetch
     int32_t slot;
-    E.actc.cur_t = t;
-    gnn_status st = acquire(c, E, E.actc, p, s, false, &slot);
+    bc.cur_t = t;
+    gnn_status st = acquire(c, E, bc, p, s, false, &slot);
     if (st != GNN_OK) return st;
     --budget;
     for (int32_t q = 0; q < k && budget > 0; ++q) {
         if (run[q + 1] - run[q] <= 0) continue;
-        if (E.actc.slot_of[(size_t)q] < 0) {
-            if ((st = acquire(c, E, E.actc, q, s, false, &slot)) != GNN_OK) return st;
+        if (bc.slot_of[(size_t)q] < 0) {
+            if ((st = acquire(c, E, bc, q, s, false, &slot)) != GNN_OK) return st;
             if (slot < 0) break;
         }
         --budget;
     }
     return GNN_OK;
+}
+
+// ---- whole arrays in the pool -----------------------------------------------------------------
+struct Key {
+    int kind, layer;
+};
+inline bool same(const Resident& r, Key key) { return r.kind == key.kind && r.layer == key.layer; }
+
+Resident* find_array(StreamEngine& E, Key key)
+{
+    for (auto& r : E.arrays)
+        if (same(*r, key)) return r.get();
+    return nullptr;
+}
+
+gnn_status release_array(gnn_ctx* c, StreamEngine& E, Resident* r)
+{
+    for (int32_t s = 0; s < r->bc.nslots; ++s)
+        if (r->bc.slots[(size_t)s].part >= 0 && r->bc.slots[(size_t)s].dirty) {
+            gnn_status st = write_back(c, E, r->bc, s);
+            if (st != GNN_OK) return st;
+        }
+    for (Slot& sl : r->bc.slots) E.spare.push_back(sl);
+    r->bc.slots.clear();
+    pool_free(E, r->off, r->bytes);
+    for (size_t i = 0; i < E.arrays.size(); ++i)
+        if (E.arrays[i].get() == r) {
+            E.arrays.erase(E.arrays.begin() + (long)i);
+            break;
+        }
+    return GNN_OK;
+}
+
+bool is_protected(const Resident& r, const Key* keep, int nkeep)
+{
+    for (int i = 0; i < nkeep; ++i)
+        if (same(r, keep[i])) return true;
+    return false;
+}
+
+// The array to give up when room is needed: among those the current phase does not use, the one
+// of the lowest layer (forward will not read it again, backward reads it last).
+Resident* pick_array_victim(StreamEngine& E, const Key* keep, int nkeep)
+{
+    Resident* v = nullptr;
+    for (auto& r : E.arrays) {
+        if (is_protected(*r, keep, nkeep)) continue;
+        if (!v || r->layer < v->layer || (r->layer == v->layer && r->kind < v->kind)) v = r.get();
+    }
+    return v;
+}
+
+// Returns the array `key` if it is in the pool, else tries to give it k slots, evicting arrays
+// the phase does not use and then, in the order given, arrays it could use but values less
+// (entries may be null; the ones given up are set to null).  `evict` = false: only take free
+// room.  *out = nullptr when it does not fit.
+gnn_status ensure_array(gnn_ctx* c, StreamEngine& E, Key key, int64_t slot_bytes, int64_t row_bytes,
+                        char* host, bool writeback, const Key* keep, int nkeep, Resident*** lesser,
+                        int nlesser, bool evict, Resident** out)
+{
+    *out = find_array(E, key);
+    if (*out) return GNN_OK;
+    slot_bytes = round256(slot_bytes);
+    const int64_t bytes = (int64_t)E.k * slot_bytes;
+    if (bytes > E.pool_bytes) return GNN_OK;
+    // worth trying only if it fits once everything that may go has gone
+    int64_t could = 0;
+    for (const auto& f : E.free_list) could += f.second;
+    for (const auto& r : E.arrays) {
+        bool may_go = evict && !is_protected(*r, keep, nkeep);
+        for (int i = 0; i < nlesser && evict; ++i)
+            if (*lesser[i] == r.get()) may_go = true;
+        if (may_go) could += r->bytes;
+    }
+    if (could < bytes) return GNN_OK;
+    int64_t off = pool_alloc(E, bytes);
+    while (off < 0 && evict) {
+        Resident* v = pick_array_victim(E, keep, nkeep);
+        for (int i = 0; i < nlesser && !v; ++i)
+            if (*lesser[i]) {
+                v = *lesser[i];
+                *lesser[i] = nullptr;
+            }
+        if (!v) return GNN_OK;
+        gnn_status st = release_array(c, E, v);
+        if (st != GNN_OK) return st;
+        off = pool_alloc(E, bytes);
+    }
+    if (off < 0) return GNN_OK;
+    std::unique_ptr<Resident> r(new Resident());
+    r->kind = key.kind;
+    r->layer = key.layer;
+    r->off = off;
+    r->bytes = bytes;
+    gnn_status st = configure(c, E, r->bc, E.pool + off, bytes, slot_bytes, row_bytes, host, writeback, true);
+    if (st != GNN_OK) {
+        pool_free(E, off, bytes);
+        return st;
+    }
+    *out = r.get();
+    E.arrays.push_back(std::move(r));
+    return GNN_OK;
+}
+
+// Frees every array except those in `keep`: a block cache is about to take what is left.
+gnn_status release_others(gnn_ctx* c, StreamEngine& E, const Key* keep, int nkeep)
+{
+    for (;;) {
+        Resident* v = pick_array_victim(E, keep, nkeep);
+        if (!v) return GNN_OK;
+        gnn_status st = release_array(c, E, v);
+        if (st != GNN_OK) return st;
+    }
 }
 
 }  // namespace
@@ -315,11 +520,10 @@ gnn_status stream_engine_create(gnn_ctx* c)
     }
     int64_t dmax = 0;
     for (int32_t d : c->dims) dmax = std::max<int64_t>(dmax, d);
-    E->io_bytes = (std::max<int64_t>(1, M.stats.max_own * dmax * 4) + 255) / 256 * 256;
-    E->pool_bytes = c->hbm_budget;
+    E->io_bytes = round256(M.stats.max_own * dmax * 4);
+    E->pool_bytes = c->hbm_budget / 256 * 256;
     // the tightest layer must still fit two activation blocks and two gradient blocks
-    const int64_t need = 2 * ((M.stats.max_own * dmax * c->es() + 255) / 256 * 256) +
-                         2 * ((M.stats.max_own * dmax * 4 + 255) / 256 * 256);
+    const int64_t need = 2 * round256(M.stats.max_own * dmax * c->es()) + 2 * round256(M.stats.max_own * dmax * 4);
     if (E->pool_bytes < need) {
         stream_engine_destroy(c);
         return c->fail(GNN_ENOMEM, "hbm_budget_bytes is too small: needs room for two activation blocks "
@@ -336,19 +540,7 @@ gnn_status stream_engine_create(gnn_ctx* c)
     if ((e = hipStreamCreate(&E->d2h)) != hipSuccess) return fail_hip(e, "hipStreamCreate");
     if ((e = hipMalloc((void**)&E->pool, (size_t)E->pool_bytes)) != hipSuccess) return fail_hip(e, "hipMalloc(block cache)");
     if ((e = hipMalloc((void**)&E->io, (size_t)(6 * E->io_bytes))) != hipSuccess) return fail_hip(e, "hipMalloc(transfer buffers)");
-    // at most one slot per partition is ever useful
-    const int64_t min_slot = std::max<int64_t>(256, M.stats.max_own * 1 * 2);
-    const int64_t max_slots = std::min<int64_t>((int64_t)M.k + 1, E->pool_bytes / min_slot + 1);
-    for (BlockCache* bc : {&E->actc, &E->gradc}) {
-        bc->slots.resize((size_t)std::max<int64_t>(2, max_slots));
-        bc->slot_of.assign((size_t)M.k, -1);
-        bc->touched.assign((size_t)M.k, 0);
-        for (Slot& s : bc->slots) {
-            if ((e = hipEventCreateWithFlags(&s.ready, hipEventDisableTiming)) != hipSuccess) return fail_hip(e, "hipEventCreate");
-            if ((e = hipEventCreateWithFlags(&s.released, hipEventDisableTiming)) != hipSuccess) return fail_hip(e, "hipEventCreate");
-            if ((e = hipEventCreateWithFlags(&s.flushed, hipEventDisableTiming)) != hipSuccess) return fail_hip(e, "hipEventCreate");
-        }
-    }
+    E->free_list.assign(1, {0, E->pool_bytes});
     for (int i = 0; i < 2; ++i) {
         if ((e = hipEventCreateWithFlags(&E->out_ready[i], hipEventDisableTiming)) != hipSuccess) return fail_hip(e, "hipEventCreate");
         if ((e = hipEventCreateWithFlags(&E->out_done[i], hipEventDisableTiming)) != hipSuccess) return fail_hip(e, "hipEventCreate");
@@ -366,12 +558,18 @@ void stream_engine_destroy(gnn_ctx* c)
     if (!E) return;
     if (E->h2d) (void)hipStreamSynchronize(E->h2d);
     if (E->d2h) (void)hipStreamSynchronize(E->d2h);
-    for (BlockCache* bc : {&E->actc, &E->gradc})
-        for (Slot& s : bc->slots) {
+    auto drop = [](std::vector<Slot>& v) {
+        for (Slot& s : v) {
             if (s.ready) (void)hipEventDestroy(s.ready);
             if (s.released) (void)hipEventDestroy(s.released);
             if (s.flushed) (void)hipEventDestroy(s.flushed);
         }
+        v.clear();
+    };
+    drop(E->actc.slots);
+    drop(E->gradc.slots);
+    drop(E->spare);
+    for (auto& r : E->arrays) drop(r->bc.slots);
     for (int i = 0; i < 2; ++i) {
         if (E->out_ready[i]) (void)hipEventDestroy(E->out_ready[i]);
         if (E->out_done[i]) (void)hipEventDestroy(E->out_done[i]);
@@ -400,18 +598,19 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
     GNN_HIP(hipEventRecord(E.layer_done, s));
     GNN_HIP(hipStreamWaitEvent(E.h2d, E.layer_done, 0));
     GNN_HIP(hipStreamWaitEvent(E.d2h, E.layer_done, 0));
-    for (BlockCache* bc : {&E.actc, &E.gradc})
-        for (Slot& sl : bc->slots) sl.has_ready = sl.has_released = sl.has_flushed = false;
+    // nothing survives from an earlier epoch: the weights, and possibly the features, have changed
+    while (!E.arrays.empty())
+        if ((st = release_array(c, E, E.arrays.back().get())) != GNN_OK) return st;
     E.has_out_done[0] = E.has_out_done[1] = false;
     E.has_in_released[0] = E.has_in_released[1] = false;
     E.h2d_bytes = E.d2h_bytes = 0;
-    for (BlockCache* bc : {&E.actc, &E.gradc}) bc->loads = bc->hits = bc->writebacks = 0;
+    E.loads[0] = E.loads[1] = E.hits[0] = E.hits[1] = E.writebacks = 0;
 
     zero_weight_grads(c, s);
 
-    // After a layer: the next layer's loads must see this layer's stores, and because the
-    // cache is re-cut into slots of another size, neither loads nor zero fills of the next
-    // layer may start before this layer's kernels and write-backs are done with the pool.
+    // Between phases: the next phase's loads must see this phase's stores, and because regions of
+    // the pool change hands, neither loads nor kernels of the next phase may start before this
+    // phase's kernels and stores are done with the pool.
     auto end_of_layer = [&]() -> gnn_status {
         GNN_HIP(hipEventRecord(E.layer_done, E.d2h));
         GNN_HIP(hipStreamWaitEvent(E.h2d, E.layer_done, 0));
@@ -435,26 +634,71 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
         if (E.has_out_done[ob]) GNN_HIP(hipStreamWaitEvent(s, E.out_done[ob], 0));
         return GNN_OK;
     };
+    // Block p of a resident array has just been produced on the compute stream: it is valid from
+    // now on, and goes to its host rows on the store stream (`bytes` of it).
+    auto produced = [&](Resident* r, int32_t p, char* dst, int64_t bytes) -> gnn_status {
+        Slot& sl = r->bc.slots[(size_t)p];
+        sl.part = p;
+        sl.dirty = false;
+        sl.has_ready = false;
+        r->bc.slot_of[(size_t)p] = p;
+        GNN_HIP(hipEventRecord(sl.released, s));
+        sl.has_released = true;
+        GNN_HIP(hipStreamWaitEvent(E.d2h, sl.released, 0));
+        if (bytes > 0) GNN_HIP(hipMemcpyAsync(dst, r->bc.ptr(p), (size_t)bytes, hipMemcpyDeviceToHost, E.d2h));
+        E.d2h_bytes += bytes;
+        return GNN_OK;
+    };
+    auto act_slot_bytes = [&](int32_t layer) {     // a block of A^layer
+        return round256(max_np * (int64_t)c->dims[(size_t)layer] * (layer == 0 ? c->es() : c->act_es(layer)));
+    };
+    auto act_row_bytes = [&](int32_t layer) {
+        return (int64_t)c->dims[(size_t)layer] * (layer == 0 ? c->es() : c->act_es(layer));
+    };
+    auto act_host = [&](int32_t layer) {
+        return layer == 0 ? const_cast<char*>(c->feat) : c->act[(size_t)layer - 1];
+    };
+    auto grad_slot_bytes = [&](int32_t layer) { return round256(max_np * (int64_t)c->dims[(size_t)layer] * 4); };
 
     // ---------------------------------------------------------------------------- forward
     for (int32_t l = 1; l <= L; ++l) {
-        const int32_t din = c->dims[(size_t)l - 1], dout = c->dims[(size_t)l];
-        st = configure(c, E.actc, E.pool, E.pool_bytes, max_np * din * c->es(), (int64_t)din * c->es(),
-                       const_cast<char*>(c->layer_input(l)), false);
-        if (st != GNN_OK) return st;
+        const int32_t dout = c->dims[(size_t)l];
+        const Key keep[2] = {{ARR_ACT, l - 1}, {ARR_ACT, l}};
+        // the layer's input as a whole array if it fits, and then its output as well; an input
+        // that does not fit is streamed through a block cache over the whole pool
+        Resident* in = nullptr;
+        Resident* out = nullptr;
+        if ((st = ensure_array(c, E, keep[0], act_slot_bytes(l - 1), act_row_bytes(l - 1), act_host(l - 1), false,
+                               keep, 2, nullptr, 0, true, &in)) != GNN_OK) return st;
+        if (in && (st = ensure_array(c, E, keep[1], act_slot_bytes(l), act_row_bytes(l), act_host(l), false, keep,
+                                     2, nullptr, 0, true, &out)) != GNN_OK) return st;
+        BlockCache* src = in ? &in->bc : &E.actc;
+        if (!in) {
+            if ((st = release_others(c, E, nullptr, 0)) != GNN_OK) return st;
+            const auto region = largest_free(E);
+            st = configure(c, E, E.actc, E.pool + region.first, region.second, act_slot_bytes(l - 1),
+                           act_row_bytes(l - 1), act_host(l - 1), false, false);
+            if (st != GNN_OK) return st;
+        }
         const int64_t out_row = (int64_t)dout * c->act_es(l);
         for (int32_t t = 0; t < k; ++t) {
             const int32_t p = M.sched[(size_t)t];
             const int64_t r0 = M.off[(size_t)p], np = M.off[(size_t)p + 1] - r0;
             int32_t own;
-            if ((st = gather_from_cache(c, E, l, t, s, &own)) != GNN_OK) return st;
-            if ((st = prefetch_for(c, E, t + 1, s)) != GNN_OK) return st;
-            const int ob = t & 1;
-            if ((st = wait_out_free(ob)) != GNN_OK) return st;
-            compute_fwd(c, l, p, E.actc.ptr(own), E.outbuf(ob), s);
-            if ((st = mark_used(c, E.actc, own, s, false)) != GNN_OK) return st;
-            E.actc.slots[(size_t)own].pinned = false;
-            if ((st = store_out(ob, c->act[(size_t)l - 1] + r0 * out_row, np * out_row)) != GNN_OK) return st;
+            if ((st = gather_from_cache(c, E, *src, l, t, s, &own)) != GNN_OK) return st;
+            if ((st = prefetch_for(c, E, *src, t + 1, s)) != GNN_OK) return st;
+            char* host_rows = c->act[(size_t)l - 1] + r0 * out_row;
+            if (out) {
+                compute_fwd(c, l, p, src->ptr(own), out->bc.ptr(p), s);
+                if ((st = produced(out, p, host_rows, np * out_row)) != GNN_OK) return st;
+            } else {
+                const int ob = t & 1;
+                if ((st = wait_out_free(ob)) != GNN_OK) return st;
+                compute_fwd(c, l, p, src->ptr(own), E.outbuf(ob), s);
+                if ((st = store_out(ob, host_rows, np * out_row)) != GNN_OK) return st;
+            }
+            if ((st = mark_used(c, *src, own, s, false)) != GNN_OK) return st;
+            src->slots[(size_t)own].pinned = false;
         }
         if ((st = end_of_layer()) != GNN_OK) return st;
     }
@@ -463,7 +707,7 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
     float* scal = (float*)(c->scratch + c->ws.scalars);
     unsigned long long* count_dev = (unsigned long long*)(scal + 16);
     float* losspart = (float*)(c->scratch + c->ws.losspart);
-    // Loads rows [r0, r0 + np) of a host array into transfer buffer `dst` on the load stream.
+    // Loads rows of a host array into transfer buffer `dst` on the load stream.
     auto load_in = [&](char* dst, const char* src, int64_t bytes, int ib, bool first) -> gnn_status {
         if (first && E.has_in_released[ib]) GNN_HIP(hipStreamWaitEvent(E.h2d, E.in_released[ib], 0));
         if (bytes > 0) GNN_HIP(hipMemcpyAsync(dst, src, (size_t)bytes, hipMemcpyHostToDevice, E.h2d));
@@ -472,23 +716,45 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
     };
     {
         const int32_t C = c->dims[(size_t)L];
+        const Key keep[3] = {{ARR_ACT, L}, {ARR_GRAD, L}, {ARR_ACT, L - 1}};
+        Resident* logits = find_array(E, keep[0]);
+        Resident* gout = nullptr;
+        // kept for the backward pass of layer L only if there is free room for it
+        if ((st = ensure_array(c, E, keep[1], grad_slot_bytes(L), (int64_t)C * 4, (char*)c->gact[(size_t)L - 1],
+                               false, keep, 3, nullptr, 0, false, &gout)) != GNN_OK) return st;
         launch_count_mask(c->mask, M.n, count_dev, s);
         int64_t nparts = 0;
         for (int32_t p = 0; p < k; ++p) {
             const int64_t r0 = M.off[(size_t)p], np = M.off[(size_t)p + 1] - r0;
             const int ib = p & 1;
-            if ((st = load_in(E.ainbuf(ib), c->act[(size_t)L - 1] + r0 * C * 4, np * C * 4, ib, true)) != GNN_OK) return st;
-            GNN_HIP(hipEventRecord(E.in_ready[ib], E.h2d));
-            GNN_HIP(hipStreamWaitEvent(s, E.in_ready[ib], 0));
-            if ((st = wait_out_free(ib)) != GNN_OK) return st;
-            {
-                Timed t(c, s, GNN_K_LOSS);
-                nparts += launch_loss_rows((const float*)E.ainbuf(ib), c->labels + r0, c->mask + r0,
-                                           (float*)E.outbuf(ib), np, C, count_dev, losspart + nparts, s);
+            const float* x;
+            const bool have = logits && logits->bc.holds(p);
+            if (have) {
+                x = (const float*)logits->bc.ptr(p);
+            } else {
+                if ((st = load_in(E.ainbuf(ib), c->act[(size_t)L - 1] + r0 * C * 4, np * C * 4, ib, true)) != GNN_OK) return st;
+                GNN_HIP(hipEventRecord(E.in_ready[ib], E.h2d));
+                GNN_HIP(hipStreamWaitEvent(s, E.in_ready[ib], 0));
+                x = (const float*)E.ainbuf(ib);
             }
-            GNN_HIP(hipEventRecord(E.in_released[ib], s));
-            E.has_in_released[ib] = true;
-            if ((st = store_out(ib, (char*)(c->gact[(size_t)L - 1] + r0 * C), np * C * 4)) != GNN_OK) return st;
+            float* g;
+            if (gout) g = (float*)gout->bc.ptr(p);
+            else {
+                if ((st = wait_out_free(ib)) != GNN_OK) return st;
+                g = (float*)E.outbuf(ib);
+            }
+            {
+                Timed timed(c, s, GNN_K_LOSS);
+                nparts += launch_loss_rows(x, c->labels + r0, c->mask + r0, g, np, C, count_dev, losspart + nparts, s);
+            }
+            if (!have) {
+                GNN_HIP(hipEventRecord(E.in_released[ib], s));
+                E.has_in_released[ib] = true;
+            }
+            char* host_rows = (char*)(c->gact[(size_t)L - 1] + r0 * C);
+            if (gout) st = produced(gout, p, host_rows, np * C * 4);
+            else st = store_out(ib, host_rows, np * C * 4);
+            if (st != GNN_OK) return st;
         }
         launch_loss_finish(losspart, nparts, count_dev, scal, s);
         if ((st = end_of_layer()) != GNN_OK) return st;
@@ -499,40 +765,86 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
         const int32_t din = c->dims[(size_t)l - 1], dout = c->dims[(size_t)l];
         const int64_t act_row = (int64_t)dout * c->act_es(l);
         const bool need_prev = l >= 2;
-        // Split of the pool between the two caches.  A gradient block that is evicted costs a
-        // write-back and a reload, an activation block only a reload: when every gradient
-        // block of the layer fits beside two activation blocks the gradient cache gets them
-        // all, otherwise two thirds of the pool.
-        int64_t act_pool = E.pool_bytes;
-        if (need_prev) {
-            const int64_t a_slot = (max_np * din * c->es() + 255) / 256 * 256;
-            const int64_t g_slot = (max_np * din * 4 + 255) / 256 * 256;
-            int64_t grad_pool = (int64_t)k * g_slot;
-            if (E.pool_bytes - grad_pool < 2 * a_slot) {
-                grad_pool = E.pool_bytes / 3 * 2 / 256 * 256;
-                grad_pool = std::min(grad_pool, E.pool_bytes - 2 * a_slot);
-                grad_pool = std::max(grad_pool, 2 * g_slot);
+        const Key keep[4] = {{ARR_GRAD, l - 1}, {ARR_ACT, l - 1}, {ARR_GRAD, l}, {ARR_ACT, l}};
+        const int64_t a_slot = act_slot_bytes(l - 1), g_slot = grad_slot_bytes(l - 1);
+        // Whole arrays where they fit: the gradient being accumulated first (a block of it that is
+        // evicted costs a write-back and a reload), then the gather source; the partition's own
+        // gradient and activation blocks are taken from arrays that are still in the pool.
+        Resident* acc = nullptr;
+        Resident* srcarr = find_array(E, keep[1]);
+        Resident* gin = find_array(E, keep[2]);
+        Resident* ain = l < L ? find_array(E, keep[3]) : nullptr;
+        {
+            Resident** lesser[3] = {&ain, &gin, &srcarr};
+            if (need_prev && (st = ensure_array(c, E, keep[0], g_slot, (int64_t)din * 4, (char*)c->gact[(size_t)l - 2],
+                                                true, keep, 4, lesser, 3, true, &acc)) != GNN_OK) return st;
+            if (!srcarr && (acc || !need_prev) &&
+                (st = ensure_array(c, E, keep[1], a_slot, act_row_bytes(l - 1), act_host(l - 1), false, keep, 4,
+                                   lesser, 2, true, &srcarr)) != GNN_OK) return st;
+        }
+        if ((need_prev && !acc) || !srcarr) {
+            // something is streamed: its block cache is worth more than the partition's own blocks
+            // staying in the pool
+            Key stay[2];
+            int nstay = 0;
+            if (acc) stay[nstay++] = keep[0];
+            if (srcarr) stay[nstay++] = keep[1];
+            if ((st = release_others(c, E, stay, nstay)) != GNN_OK) return st;
+            gin = ain = nullptr;
+            const int64_t need = (need_prev && !acc ? 2 * g_slot : 0) + (!srcarr ? 2 * a_slot : 0);
+            if (largest_free(E).second < need && srcarr) {
+                if ((st = release_array(c, E, srcarr)) != GNN_OK) return st;
+                srcarr = nullptr;
             }
-            act_pool = (E.pool_bytes - grad_pool) / 256 * 256;
+            if (largest_free(E).second < (need_prev && !acc ? 2 * g_slot : 0) + (!srcarr ? 2 * a_slot : 0) && acc) {
+                if ((st = release_array(c, E, acc)) != GNN_OK) return st;
+                acc = nullptr;
+            }
         }
-        st = configure(c, E.actc, E.pool, act_pool, max_np * din * c->es(), (int64_t)din * c->es(),
-                       const_cast<char*>(c->layer_input(l)), false);
-        if (st != GNN_OK) return st;
-        if (need_prev) {
-            st = configure(c, E.gradc, E.pool + act_pool, E.pool_bytes - act_pool, max_np * din * 4,
-                           (int64_t)din * 4, (char*)c->gact[(size_t)l - 2], true);
-            if (st != GNN_OK) return st;
+        BlockCache* src = srcarr ? &srcarr->bc : &E.actc;
+        BlockCache* dst = acc ? &acc->bc : &E.gradc;
+        {
+            const bool stream_acc = need_prev && !acc, stream_src = !srcarr;
+            const auto region = largest_free(E);
+            int64_t grad_bytes = 0;
+            if (stream_acc && stream_src) {
+                // a gradient block that is evicted costs two transfers, an activation block one:
+                // all k gradient blocks when they fit beside two activation blocks, else two thirds
+                grad_bytes = (int64_t)k * g_slot;
+                if (region.second - grad_bytes < 2 * a_slot) {
+                    grad_bytes = region.second / 3 * 2 / 256 * 256;
+                    grad_bytes = std::min(grad_bytes, region.second - 2 * a_slot);
+                    grad_bytes = std::max(grad_bytes, 2 * g_slot);
+                }
+            } else if (stream_acc) {
+                grad_bytes = region.second;
+            }
+            if (stream_src) {
+                st = configure(c, E, E.actc, E.pool + region.first, (region.second - grad_bytes) / 256 * 256, a_slot,
+                               act_row_bytes(l - 1), act_host(l - 1), false, false);
+                if (st != GNN_OK) return st;
+            }
+            if (stream_acc) {
+                st = configure(c, E, E.gradc, E.pool + region.first + (region.second - grad_bytes), grad_bytes,
+                               g_slot, (int64_t)din * 4, (char*)c->gact[(size_t)l - 2], true, false);
+                if (st != GNN_OK) return st;
+            }
         }
-        // transfer buffers of partition p: its gradient block and (hidden layers) its activations
+        // transfer buffers of the partition of step t: its gradient block and (hidden layers) its
+        // activations, unless they are in the pool already
         auto load_io = [&](int32_t t) -> gnn_status {
             const int32_t p = M.sched[(size_t)t];
             const int64_t r0 = M.off[(size_t)p], np = M.off[(size_t)p + 1] - r0;
             const int ib = t & 1;
-            gnn_status r = load_in(E.ginbuf(ib), (const char*)(c->gact[(size_t)l - 1] + r0 * dout),
-                                   np * dout * 4, ib, true);
-            if (r != GNN_OK) return r;
-            if (l < L) {
-                r = load_in(E.ainbuf(ib), c->act[(size_t)l - 1] + r0 * act_row, np * act_row, ib, false);
+            bool first = true;
+            if (!(gin && gin->bc.holds(p))) {
+                gnn_status r = load_in(E.ginbuf(ib), (const char*)(c->gact[(size_t)l - 1] + r0 * dout),
+                                       np * dout * 4, ib, first);
+                if (r != GNN_OK) return r;
+                first = false;
+            }
+            if (l < L && !(ain && ain->bc.holds(p))) {
+                gnn_status r = load_in(E.ainbuf(ib), c->act[(size_t)l - 1] + r0 * act_row, np * act_row, ib, first);
                 if (r != GNN_OK) return r;
             }
             GNN_HIP(hipEventRecord(E.in_ready[ib], E.h2d));
@@ -544,51 +856,59 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
             const int64_t np = M.off[(size_t)p + 1] - M.off[(size_t)p];
             const int ib = t & 1;
             int32_t own;
-            if ((st = gather_from_cache(c, E, l, t, s, &own)) != GNN_OK) return st;
-            if ((st = prefetch_for(c, E, t + 1, s)) != GNN_OK) return st;
+            if ((st = gather_from_cache(c, E, *src, l, t, s, &own)) != GNN_OK) return st;
+            if ((st = prefetch_for(c, E, *src, t + 1, s)) != GNN_OK) return st;
             if (t + 1 < k && (st = load_io(t + 1)) != GNN_OK) return st;
             GNN_HIP(hipStreamWaitEvent(s, E.in_ready[ib], 0));
-            const char* dY = compute_bwd(c, l, p, E.actc.ptr(own), (const float*)E.ginbuf(ib),
-                                         l < L ? E.ainbuf(ib) : nullptr, nullptr, s);
-            if ((st = mark_used(c, E.actc, own, s, false)) != GNN_OK) return st;
-            E.actc.slots[(size_t)own].pinned = false;
+            const float* g_own = gin && gin->bc.holds(p) ? (const float*)gin->bc.ptr(p) : (const float*)E.ginbuf(ib);
+            const char* a_own = nullptr;
+            if (l < L) a_own = ain && ain->bc.holds(p) ? ain->bc.ptr(p) : E.ainbuf(ib);
+            const char* dY = compute_bwd(c, l, p, src->ptr(own), g_own, a_own, nullptr, s);
+            if ((st = mark_used(c, *src, own, s, false)) != GNN_OK) return st;
+            src->slots[(size_t)own].pinned = false;
             if (need_prev) {
                 // scatter-accumulate the gradient of the gathered rows, owner block by owner block
                 const float* dGA = (const float*)(c->scratch + c->ws.dga);
                 const int64_t* run = M.brun.data() + (size_t)p * ((size_t)k + 1);
                 const int64_t b0 = M.boff[(size_t)p];
                 int32_t gown;
-                E.gradc.cur_t = t;
-                if ((st = acquire(c, E, E.gradc, p, s, true, &gown)) != GNN_OK) return st;
-                E.gradc.slots[(size_t)gown].pinned = true;
+                dst->cur_t = t;
+                if ((st = acquire(c, E, *dst, p, s, true, &gown)) != GNN_OK) return st;
+                dst->slots[(size_t)gown].pinned = true;
                 {
                     Timed timed(c, s, GNN_K_SCATTER);
-                    launch_scatter_add(dGA, np, np, 0, nullptr, (float*)E.gradc.ptr(gown), din, s);
+                    launch_scatter_add(dGA, np, np, 0, nullptr, (float*)dst->ptr(gown), din, s);
                     for (int32_t q = 0; q < k; ++q) {
                         const int64_t len = run[q + 1] - run[q];
                         if (len <= 0) continue;
                         int32_t gq;
-                        if ((st = acquire(c, E, E.gradc, q, s, true, &gq)) != GNN_OK) return st;
+                        if ((st = acquire(c, E, *dst, q, s, true, &gq)) != GNN_OK) return st;
                         launch_scatter_add(dGA + (np + run[q]) * din, len, 0, 0, c->D.bnd_local + b0 + run[q],
-                                           (float*)E.gradc.ptr(gq), din, s);
-                        if ((st = mark_used(c, E.gradc, gq, s, true)) != GNN_OK) return st;
+                                           (float*)dst->ptr(gq), din, s);
+                        if ((st = mark_used(c, *dst, gq, s, true)) != GNN_OK) return st;
                     }
                 }
-                compute_bwd_self(c, l, p, dY, (float*)E.gradc.ptr(gown), s);
-                if ((st = mark_used(c, E.gradc, gown, s, true)) != GNN_OK) return st;
-                E.gradc.slots[(size_t)gown].pinned = false;
+                compute_bwd_self(c, l, p, dY, (float*)dst->ptr(gown), s);
+                if ((st = mark_used(c, *dst, gown, s, true)) != GNN_OK) return st;
+                dst->slots[(size_t)gown].pinned = false;
             }
             // dY may alias the gradient transfer buffer: release it only now
             GNN_HIP(hipEventRecord(E.in_released[ib], s));
             E.has_in_released[ib] = true;
         }
         if (need_prev) {
-            // end of the layer: every gradient block goes back to its host rows
-            for (int32_t sidx = 0; sidx < E.gradc.nslots; ++sidx)
-                if (E.gradc.slots[(size_t)sidx].part >= 0 && E.gradc.slots[(size_t)sidx].dirty)
-                    if ((st = write_back(c, E, E.gradc, sidx)) != GNN_OK) return st;
+            // end of the layer: every gradient block goes back to its host rows (and, in a whole
+            // array, stays where it is for the next layer's backward pass)
+            for (int32_t sidx = 0; sidx < dst->nslots; ++sidx)
+                if (dst->slots[(size_t)sidx].part >= 0 && dst->slots[(size_t)sidx].dirty)
+                    if ((st = write_back(c, E, *dst, sidx)) != GNN_OK) return st;
         }
         if ((st = end_of_layer()) != GNN_OK) return st;
+        // grad A^l and A^l are dead from here on
+        if (Resident* r = find_array(E, keep[2]))
+            if ((st = release_array(c, E, r)) != GNN_OK) return st;
+        if (Resident* r = find_array(E, keep[3]))
+            if ((st = release_array(c, E, r)) != GNN_OK) return st;
     }
 
     GNN_HIP(hipStreamSynchronize(s));
@@ -596,11 +916,11 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
     GNN_HIP(hipStreamSynchronize(E.d2h));
     GNN_HIP(hipMemcpy(loss_out, scal, sizeof(float), hipMemcpyDeviceToHost));
     c->loss_done = true;
-    c->stream_stats.act_loads = E.actc.loads;
-    c->stream_stats.act_hits = E.actc.hits;
-    c->stream_stats.grad_loads = E.gradc.loads;
-    c->stream_stats.grad_hits = E.gradc.hits;
-    c->stream_stats.grad_writebacks = E.gradc.writebacks;
+    c->stream_stats.act_loads = E.loads[0];
+    c->stream_stats.act_hits = E.hits[0];
+    c->stream_stats.grad_loads = E.loads[1];
+    c->stream_stats.grad_hits = E.hits[1];
+    c->stream_stats.grad_writebacks = E.writebacks;
     c->stream_stats.h2d_bytes = E.h2d_bytes;
     c->stream_stats.d2h_bytes = E.d2h_bytes;
     return check_launch(c, "gnn_epoch (streaming)");
