@@ -132,6 +132,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--partitioner", choices=["random", "lp", "switching", "switching_device"], default=None,
                     help="override the workload's partitioner")
+    ap.add_argument("--graph-scale", type=float, default=1.0,
+                    help="shrink the workload's graph (vertices and drawn edges) by this factor; "
+                         "for runs that would not fit the host otherwise")
     ap.add_argument("--train", action="store_true",
                     help="time training steps instead of bare epochs: epoch with dropout 0.5 after "
                          "the hidden layers, then one Adam step (lr 0.01), as in the paper's runs")
@@ -160,7 +163,11 @@ def main():
         sys.exit("bench.py: no GPU visible")
 
     t0 = time.perf_counter()
-    cfg, rowptr, colidx = make_config(args.workload)
+    over = {}
+    if args.graph_scale != 1.0:
+        base = CONFIGS[args.workload]
+        over = {"n": int(base["n"] * args.graph_scale), "m_draw": int(base["m_draw"] * args.graph_scale)}
+    cfg, rowptr, colidx = make_config(args.workload, **over)
     n, dims, model = cfg["n"], cfg["dims"], cfg["model"]
     log("graph %s: n=%d entries=%d (%.1f s)" % (args.workload, n, rowptr[-1], time.perf_counter() - t0))
     X = features(n, dims[0], cfg["seed"])
@@ -173,7 +180,7 @@ def main():
         cfg["part"] = args.partitioner
     s = Session(model, dims, rowptr, colidx, cfg["k"], cfg["part"], cfg["seed"], X, w, y, m,
                 dtype=cfg["dtype"], hbm_budget_bytes=int(args.hbm_budget_gb * 2 ** 30),
-                layer_order=args.layer_order)
+                layer_order=args.layer_order, progress=lambda msg: log("  " + msg))
     xf = [s.ctx.layer_is_transform_first(l) for l in range(1, len(dims))]
     es = 2 if cfg["dtype"] == "bf16" else 4
     mfma_peak = MFMA_BF16_PEAK_TFLOPS if cfg["dtype"] == "bf16" else MFMA_F32_PEAK_TFLOPS
@@ -227,7 +234,8 @@ def main():
         "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg["dtype"], "data": "synthetic",
-        "config": {"workload": args.workload + ("" if not args.hbm_budget_gb else
+        "config": {"workload": args.workload + ("" if args.graph_scale == 1.0 else " x%g" % args.graph_scale) +
+                   ("" if not args.hbm_budget_gb else
                                                  " (streaming, %.3g GiB block cache)" % args.hbm_budget_gb),
                    "n": n, "operator_entries": nnz, "model": model,
                    "dims": list(dims), "k": stats["k"], "partitioner": cfg["part"],

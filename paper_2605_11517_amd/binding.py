@@ -300,7 +300,7 @@ class Session:
 
     def __init__(self, model, dims, rowptr, colidx, k, part_mode, seed, X, weights, labels,
                  train_mask, has_bias=True, user_part=None, device="cuda:0", dtype="f32",
-                 hbm_budget_bytes=0, layer_order="aggregate"):
+                 hbm_budget_bytes=0, layer_order="aggregate", progress=None):
         import torch
         self.torch = torch
         if not torch.cuda.is_available():
@@ -314,7 +314,9 @@ class Session:
         self.ctx = Context(model, dims, dtype=GNN_BF16 if self.bf16 else GNN_F32, has_bias=has_bias,
                            hbm_budget_bytes=hbm_budget_bytes)
         self.ctx.set_layer_order(layer_order)
+        say = progress or (lambda msg: None)
         self.ctx.build_partitions(rowptr, colidx, k, part_mode, seed, user_part)
+        say("partitions built")
         self.model = _MODEL.get(model, model)
         self.dims = list(dims)
         self.L = len(dims) - 1
@@ -335,9 +337,13 @@ class Session:
             big = dict(device=self.dev)
             self.feat = self._to_library(
                 t.from_numpy(np.ascontiguousarray(X, dtype=np.float32)).to(store))
-        self.act = [t.zeros((self.n, dims[l + 1]), dtype=store if l < self.L - 1 else t.float32, **big)
-                    for l in range(self.L)]                                  # logits stay fp32
-        self.gact = [t.zeros((self.n, dims[l + 1]), dtype=t.float32, **big) for l in range(self.L)]
+        say("features placed")
+        self.act, self.gact = [], []
+        for l in range(self.L):
+            self.act.append(t.zeros((self.n, dims[l + 1]), dtype=store if l < self.L - 1 else t.float32,
+                                    **big))                                  # logits stay fp32
+            self.gact.append(t.zeros((self.n, dims[l + 1]), dtype=t.float32, **big))
+            say("buffers of layer %d allocated" % (l + 1))
         self.w, self.gw = [], []
         for l in range(self.L):
             for key in ("W", "Ws", "b"):
@@ -363,6 +369,7 @@ class Session:
         self.ctx.bind(ptr(self.feat), [ptr(a) for a in self.act], [ptr(g) for g in self.gact],
                       [ptr(w) for w in self.w], [ptr(g) for g in self.gw], ptr(self.labels),
                       ptr(self.mask), ptr(self.staging), ptr(self.scratch))
+        say("bound")
         t.cuda.synchronize()
         del stream
 

@@ -31,6 +31,7 @@ void free_device(DevMeta& D)
     if (D.rscale) (void)hipFree(D.rscale);
     if (D.bnd) (void)hipFree(D.bnd);
     if (D.bnd_local) (void)hipFree(D.bnd_local);
+    if (D.bnd_flat) (void)hipFree(D.bnd_flat);
     if (D.trp) (void)hipFree(D.trp);
     if (D.tcol) (void)hipFree(D.tcol);
     if (D.tw) (void)hipFree(D.tw);
@@ -72,6 +73,7 @@ gnn_status ensure_device(gnn_ctx* c)
     step(upload(D.rscale, M.rscale));
     step(upload(D.bnd, M.bnd));
     step(upload(D.bnd_local, M.bnd_local));
+    step(upload(D.bnd_flat, M.bnd_flat));
     step(upload(D.trp, M.trp));
     step(upload(D.tcol, M.tcol));
     step(upload(D.tw, M.tw));
@@ -288,7 +290,7 @@ void compute_fwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, char*
 }
 
 const char* compute_bwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, const float* g_own,
-                        const char* act_own, float* fused_gprev, hipStream_t s)
+                        const char* act_own, float* fused_gprev, const SpmmScatter* fused_map, hipStream_t s)
 {
     const HostMeta& M = c->M;
     const int32_t L = c->L;
@@ -358,6 +360,7 @@ const char* compute_bwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own
             sc.n_own = np;
             sc.base_row = M.off[(size_t)p];
             sc.idx = c->D.bnd + M.boff[(size_t)p];
+            if (fused_map) sc = *fused_map;      // another row numbering of the same owners
             out = fused_gprev;
         }
         {
@@ -1048,7 +1051,7 @@ gnn_status gnn_layer_bwd(gnn_ctx* c, int32_t layer, int32_t p, void* stream)
     }();
     float* gprev = layer >= 2 ? c->gact[(size_t)layer - 2] : nullptr;
     const char* dY = compute_bwd(c, layer, p, c->layer_input(layer, r0),
-                                 c->gact[(size_t)layer - 1] + r0 * dout, act_own, fuse ? gprev : nullptr, s);
+                                 c->gact[(size_t)layer - 1] + r0 * dout, act_own, fuse ? gprev : nullptr, nullptr, s);
     if (layer >= 2) {
         if (!fuse) {
             Timed t(c, s, GNN_K_SCATTER);

@@ -17,6 +17,7 @@ struct DevMeta {
     float* rscale = nullptr;
     int32_t* bnd = nullptr;
     int32_t* bnd_local = nullptr;
+    int32_t* bnd_flat = nullptr;
     int64_t* trp = nullptr;
     int32_t* tcol = nullptr;
     float* tw = nullptr;
@@ -170,9 +171,10 @@ void compute_fwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, char*
 // Activation backward, recompute of Z_p, weight/bias gradients (added into grad_w) and, for
 // layer >= 2, dZ_p and the gradient of the gathered rows (left in scratch, |R_p| x d_{l-1}
 // fp32), or, when fused_gprev (the full grad A^{l-1} array) is given, added straight onto its
-// owner rows there.  Returns the dY_p block (dtype of the context; fp32 path: may alias g_own).
+// owner rows there (rows in library order, or as numbered by fused_map when that is given).
+// Returns the dY_p block (dtype of the context; fp32 path: may alias g_own).
 const char* compute_bwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, const float* g_own,
-                        const char* act_own, float* fused_gprev, hipStream_t s);
+                        const char* act_own, float* fused_gprev, const SpmmScatter* fused_map, hipStream_t s);
 // SAGE self term: gprev_own (n_p x d_{l-1} fp32) += dY_p W_s^T
 void compute_bwd_self(gnn_ctx* c, int32_t layer, int32_t p, const char* dY, float* gprev_own,
                       hipStream_t s);

@@ -34,6 +34,8 @@ struct HostMeta {
     // only when the streaming schedule is requested: B_p split by source partition
     std::vector<int32_t> bnd_local; // row inside its source partition's block
     std::vector<int64_t> brun;      // k * (k+1): brun[p*(k+1)+q] = first entry of B_p owned by q
+    std::vector<int32_t> bnd_flat;  // source partition * max_own + row inside its block (arrays whose
+                                    // blocks are max_own rows apart); empty if that overflows int32
     // transpose of S per partition: rows are the entries of R_p = [own_p ; B_p]
     std::vector<int64_t> toff;      // k+1, offset of partition p's rows in trp
     std::vector<int64_t> trp;       // sum |R_p| + 1, positions into tcol / tw

@@ -617,6 +617,19 @@ gnn_status build_host_meta(int model, int64_t n, const int64_t* rowptr, const in
                     for (int64_t i = run[q]; i < run[q + 1]; ++i)
                         M.bnd_local[(size_t)(M.boff[(size_t)p] + i)] = b0[i] - (int32_t)M.off[(size_t)q];
             });
+            int64_t max_own = 0;
+            for (int32_t p = 0; p < k; ++p) max_own = std::max(max_own, M.off[(size_t)p + 1] - M.off[(size_t)p]);
+            if ((int64_t)k * max_own < 0x7FFFFFF0ll) {
+                M.bnd_flat.resize(M.bnd.size());
+                parallel_for(k, 1, [&](int, int64_t p) {
+                    const int64_t* run = M.brun.data() + (size_t)p * ((size_t)k + 1);
+                    for (int32_t q = 0; q < k; ++q)
+                        for (int64_t i = run[q]; i < run[q + 1]; ++i) {
+                            const size_t at = (size_t)(M.boff[(size_t)p] + i);
+                            M.bnd_flat[at] = (int32_t)((int64_t)q * max_own + M.bnd_local[at]);
+                        }
+                });
+            }
         }
 
         // ---- order in which an epoch walks the partitions -------------------------------------

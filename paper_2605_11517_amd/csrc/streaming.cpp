@@ -46,6 +46,7 @@ struct Slot {
     hipEvent_t released = nullptr;  // recorded on the compute stream after the last kernel using it
     hipEvent_t flushed = nullptr;   // recorded on the store stream after a write-back
     bool has_ready = false, has_released = false, has_flushed = false;
+    bool waited = false;            // the compute stream has already waited for `ready`
 };
 
 struct BlockCache {
@@ -163,6 +164,7 @@ gnn_status new_slot(gnn_ctx* c, StreamEngine& E, Slot& out)
     out.dirty = out.pinned = false;
     out.last_use = 0;
     out.has_ready = out.has_released = out.has_flushed = false;
+    out.waited = false;
     return GNN_OK;
 }
 
@@ -170,7 +172,9 @@ gnn_status new_slot(gnn_ctx* c, StreamEngine& E, Slot& out)
 gnn_status configure(gnn_ctx* c, StreamEngine& E, BlockCache& bc, char* pool, int64_t pool_bytes,
                      int64_t slot_bytes, int64_t row_bytes, char* host, bool writeback, bool identity)
 {
-    slot_bytes = round256(slot_bytes);
+    // blocks of a whole array lie exactly max_own rows apart, so that one flat row index reaches
+    // every block; the slots of a block cache start on 256-byte boundaries
+    if (!identity) slot_bytes = round256(slot_bytes);
     int64_t n = pool_bytes / slot_bytes;
     if (n < 2 && !identity)
         return c->fail(GNN_ENOMEM, "hbm_budget_bytes is too small: a block cache needs room for two "
@@ -199,6 +203,7 @@ gnn_status configure(gnn_ctx* c, StreamEngine& E, BlockCache& bc, char* pool, in
         s.dirty = s.pinned = false;
         s.last_use = 0;
         s.has_ready = s.has_released = s.has_flushed = false;
+        s.waited = false;
     }
     bc.slot_of.assign((size_t)E.k, -1);
     bc.touched.assign((size_t)E.k, 0);
@@ -298,6 +303,7 @@ gnn_status acquire(gnn_ctx* c, StreamEngine& E, BlockCache& bc, int32_t part, hi
             if (sl.has_flushed) GNN_HIP(hipStreamWaitEvent(compute, sl.flushed, 0));
             launch_fill_zero(bc.ptr(s), np * bc.row_bytes, compute);
             sl.has_ready = false;
+            sl.waited = false;
         } else {
             if (sl.has_released) GNN_HIP(hipStreamWaitEvent(E.h2d, sl.released, 0));
             if (sl.has_flushed) GNN_HIP(hipStreamWaitEvent(E.h2d, sl.flushed, 0));
@@ -306,6 +312,7 @@ gnn_status acquire(gnn_ctx* c, StreamEngine& E, BlockCache& bc, int32_t part, hi
                                        hipMemcpyHostToDevice, E.h2d));
             GNN_HIP(hipEventRecord(sl.ready, E.h2d));
             sl.has_ready = true;
+            sl.waited = false;
             ++E.loads[kind];
             E.h2d_bytes += np * bc.row_bytes;
         }
@@ -316,7 +323,10 @@ gnn_status acquire(gnn_ctx* c, StreamEngine& E, BlockCache& bc, int32_t part, hi
     }
     Slot& sl = bc.slots[(size_t)s];
     sl.last_use = ++bc.tick;
-    if (wait && sl.has_ready) GNN_HIP(hipStreamWaitEvent(compute, sl.ready, 0));
+    if (wait && sl.has_ready && !sl.waited) {
+        GNN_HIP(hipStreamWaitEvent(compute, sl.ready, 0));
+        sl.waited = true;
+    }
     *slot_out = s;
     return GNN_OK;
 }
@@ -324,9 +334,10 @@ gnn_status acquire(gnn_ctx* c, StreamEngine& E, BlockCache& bc, int32_t part, hi
 gnn_status mark_used(gnn_ctx* c, BlockCache& bc, int32_t s, hipStream_t compute, bool dirty)
 {
     Slot& sl = bc.slots[(size_t)s];
+    if (dirty) sl.dirty = true;
+    if (bc.identity) return GNN_OK;      // never evicted: nothing has to wait for its last reader
     GNN_HIP(hipEventRecord(sl.released, compute));
     sl.has_released = true;
-    if (dirty) sl.dirty = true;
     return GNN_OK;
 }
 
@@ -345,15 +356,19 @@ gnn_status gather_from_cache(gnn_ctx* c, StreamEngine& E, BlockCache& bc, int32_
     const int64_t* run = M.brun.data() + (size_t)p * ((size_t)k + 1);
     const int64_t b0 = M.boff[(size_t)p];
     Timed timed(c, s, GNN_K_GATHER);
+    const bool flat = bc.identity && c->D.bnd_flat;
     for (int32_t q = 0; q < k; ++q) {
         const int64_t len = run[q + 1] - run[q];
         if (len <= 0) continue;
         int32_t sq;
         if ((st = acquire(c, E, bc, q, s, true, &sq)) != GNN_OK) return st;
+        if (flat) continue;
         launch_gather_rows(bc.ptr(sq), c->D.bnd_local + b0 + run[q], c->staging + run[q] * row_bytes,
                            len, row_bytes, s);
         if ((st = mark_used(c, bc, sq, s, false)) != GNN_OK) return st;
     }
+    // a whole array: every block is in place, one launch gathers across all of them
+    if (flat) launch_gather_rows(bc.pool, c->D.bnd_flat + b0, c->staging, M.boff[(size_t)p + 1] - b0, row_bytes, s);
     return GNN_OK;
 }
 
@@ -443,8 +458,7 @@ gnn_status ensure_array(gnn_ctx* c, StreamEngine& E, Key key, int64_t slot_bytes
 {
     *out = find_array(E, key);
     if (*out) return GNN_OK;
-    slot_bytes = round256(slot_bytes);
-    const int64_t bytes = (int64_t)E.k * slot_bytes;
+    const int64_t bytes = round256((int64_t)E.k * slot_bytes);
     if (bytes > E.pool_bytes) return GNN_OK;
     // worth trying only if it fits once everything that may go has gone
     int64_t could = 0;
@@ -650,7 +664,7 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
         return GNN_OK;
     };
     auto act_slot_bytes = [&](int32_t layer) {     // a block of A^layer
-        return round256(max_np * (int64_t)c->dims[(size_t)layer] * (layer == 0 ? c->es() : c->act_es(layer)));
+        return std::max<int64_t>(1, max_np) * (int64_t)c->dims[(size_t)layer] * (layer == 0 ? c->es() : c->act_es(layer));
     };
     auto act_row_bytes = [&](int32_t layer) {
         return (int64_t)c->dims[(size_t)layer] * (layer == 0 ? c->es() : c->act_es(layer));
@@ -658,7 +672,9 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
     auto act_host = [&](int32_t layer) {
         return layer == 0 ? const_cast<char*>(c->feat) : c->act[(size_t)layer - 1];
     };
-    auto grad_slot_bytes = [&](int32_t layer) { return round256(max_np * (int64_t)c->dims[(size_t)layer] * 4); };
+    auto grad_slot_bytes = [&](int32_t layer) {
+        return std::max<int64_t>(1, max_np) * (int64_t)c->dims[(size_t)layer] * 4;
+    };
 
     // ---------------------------------------------------------------------------- forward
     for (int32_t l = 1; l <= L; ++l) {
@@ -758,6 +774,8 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
         }
         launch_loss_finish(losspart, nparts, count_dev, scal, s);
         if ((st = end_of_layer()) != GNN_OK) return st;
+        // the logits are not read again (the output layer has no activation to differentiate)
+        if (logits && (st = release_array(c, E, logits)) != GNN_OK) return st;
     }
 
     // --------------------------------------------------------------------------- backward
@@ -767,6 +785,7 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
         const bool need_prev = l >= 2;
         const Key keep[4] = {{ARR_GRAD, l - 1}, {ARR_ACT, l - 1}, {ARR_GRAD, l}, {ARR_ACT, l}};
         const int64_t a_slot = act_slot_bytes(l - 1), g_slot = grad_slot_bytes(l - 1);
+        const int64_t a_blk = round256(a_slot), g_blk = round256(g_slot);      // slots of a block cache
         // Whole arrays where they fit: the gradient being accumulated first (a block of it that is
         // evicted costs a write-back and a reload), then the gather source; the partition's own
         // gradient and activation blocks are taken from arrays that are still in the pool.
@@ -791,12 +810,12 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
             if (srcarr) stay[nstay++] = keep[1];
             if ((st = release_others(c, E, stay, nstay)) != GNN_OK) return st;
             gin = ain = nullptr;
-            const int64_t need = (need_prev && !acc ? 2 * g_slot : 0) + (!srcarr ? 2 * a_slot : 0);
+            const int64_t need = (need_prev && !acc ? 2 * g_blk : 0) + (!srcarr ? 2 * a_blk : 0);
             if (largest_free(E).second < need && srcarr) {
                 if ((st = release_array(c, E, srcarr)) != GNN_OK) return st;
                 srcarr = nullptr;
             }
-            if (largest_free(E).second < (need_prev && !acc ? 2 * g_slot : 0) + (!srcarr ? 2 * a_slot : 0) && acc) {
+            if (largest_free(E).second < (need_prev && !acc ? 2 * g_blk : 0) + (!srcarr ? 2 * a_blk : 0) && acc) {
                 if ((st = release_array(c, E, acc)) != GNN_OK) return st;
                 acc = nullptr;
             }
@@ -810,11 +829,11 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
             if (stream_acc && stream_src) {
                 // a gradient block that is evicted costs two transfers, an activation block one:
                 // all k gradient blocks when they fit beside two activation blocks, else two thirds
-                grad_bytes = (int64_t)k * g_slot;
-                if (region.second - grad_bytes < 2 * a_slot) {
+                grad_bytes = (int64_t)k * g_blk;
+                if (region.second - grad_bytes < 2 * a_blk) {
                     grad_bytes = region.second / 3 * 2 / 256 * 256;
-                    grad_bytes = std::min(grad_bytes, region.second - 2 * a_slot);
-                    grad_bytes = std::max(grad_bytes, 2 * g_slot);
+                    grad_bytes = std::min(grad_bytes, region.second - 2 * a_blk);
+                    grad_bytes = std::max(grad_bytes, 2 * g_blk);
                 }
             } else if (stream_acc) {
                 grad_bytes = region.second;
@@ -863,15 +882,36 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
             const float* g_own = gin && gin->bc.holds(p) ? (const float*)gin->bc.ptr(p) : (const float*)E.ginbuf(ib);
             const char* a_own = nullptr;
             if (l < L) a_own = ain && ain->bc.holds(p) ? ain->bc.ptr(p) : E.ainbuf(ib);
-            const char* dY = compute_bwd(c, l, p, src->ptr(own), g_own, a_own, nullptr, s);
+            // The accumulator as a whole array: the transposed aggregation adds its rows straight
+            // onto their owners, as in the resident schedule, once every owner block exists.
+            const bool fused = need_prev && acc && c->D.bnd_flat;
+            const int64_t* run = M.brun.data() + (size_t)p * ((size_t)k + 1);
+            const int64_t b0 = M.boff[(size_t)p];
+            int32_t gown = -1;
+            SpmmScatter map;
+            if (fused) {
+                dst->cur_t = t;
+                if ((st = acquire(c, E, *dst, p, s, true, &gown)) != GNN_OK) return st;
+                if ((st = mark_used(c, *dst, gown, s, true)) != GNN_OK) return st;
+                for (int32_t q = 0; q < k; ++q) {
+                    if (run[q + 1] - run[q] <= 0) continue;
+                    int32_t gq;
+                    if ((st = acquire(c, E, *dst, q, s, true, &gq)) != GNN_OK) return st;
+                    if ((st = mark_used(c, *dst, gq, s, true)) != GNN_OK) return st;
+                }
+                map.n_own = np;
+                map.base_row = (int64_t)p * max_np;
+                map.idx = c->D.bnd_flat + b0;
+            }
+            const char* dY = compute_bwd(c, l, p, src->ptr(own), g_own, a_own, fused ? (float*)dst->pool : nullptr,
+                                         fused ? &map : nullptr, s);
             if ((st = mark_used(c, *src, own, s, false)) != GNN_OK) return st;
             src->slots[(size_t)own].pinned = false;
-            if (need_prev) {
+            if (fused) {
+                compute_bwd_self(c, l, p, dY, (float*)dst->ptr(gown), s);
+            } else if (need_prev) {
                 // scatter-accumulate the gradient of the gathered rows, owner block by owner block
                 const float* dGA = (const float*)(c->scratch + c->ws.dga);
-                const int64_t* run = M.brun.data() + (size_t)p * ((size_t)k + 1);
-                const int64_t b0 = M.boff[(size_t)p];
-                int32_t gown;
                 dst->cur_t = t;
                 if ((st = acquire(c, E, *dst, p, s, true, &gown)) != GNN_OK) return st;
                 dst->slots[(size_t)gown].pinned = true;
@@ -899,6 +939,10 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
         if (need_prev) {
             // end of the layer: every gradient block goes back to its host rows (and, in a whole
             // array, stays where it is for the next layer's backward pass)
+            if (dst->identity) {
+                GNN_HIP(hipEventRecord(E.compute_done, s));
+                GNN_HIP(hipStreamWaitEvent(E.d2h, E.compute_done, 0));
+            }
             for (int32_t sidx = 0; sidx < dst->nslots; ++sidx)
                 if (dst->slots[(size_t)sidx].part >= 0 && dst->slots[(size_t)sidx].dirty)
                     if ((st = write_back(c, E, *dst, sidx)) != GNN_OK) return st;
