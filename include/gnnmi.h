@@ -256,8 +256,12 @@ gnn_status gnn_epoch(gnn_ctx *ctx, void *stream, float *loss_out);
  * aggregate and scatter-accumulate at the output width, with no regather and no recompute in
  * the backward pass (it needs only the partition's own rows of A^{l-1} and the gradient of H).
  *   GNN_ORDER_AGGREGATE_FIRST (default): every layer as in the paper.
- *   GNN_ORDER_AUTO: layers with d_l < d_{l-1} transform first (resident schedule, GNN_F32;
- *     other layers and configurations keep the paper's order).
+ *   GNN_ORDER_AUTO: a layer transforms first when that moves fewer rows: 2 d_l < 3 d_{l-1}
+ *     (layer 1, which needs no input gradient: 2 d_l < 2 d_{l-1}); aggregating first reads
+ *     input-wide rows forward, again in the recompute and once more transposed, transforming
+ *     first aggregates output-wide rows once forward and once transposed.  Resident schedule;
+ *     with GNN_BF16 only a narrowing output layer of whole 16-byte rows.  Other layers and
+ *     configurations keep the paper's order.
  * Changes the workspace sizes: call before gnn_workspace_bytes / gnn_bind (a bound context
  * becomes unbound).  Results differ from the other order only by rounding. */
 typedef enum { GNN_ORDER_AGGREGATE_FIRST = 0, GNN_ORDER_AUTO = 1 } gnn_layer_order;

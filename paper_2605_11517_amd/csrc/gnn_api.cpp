@@ -139,8 +139,10 @@ void compute_workspace(gnn_ctx* c)
         if (c->transform_first(l)) hp = std::max<int64_t>(hp, c->padded(l));
     w.h = w.gh = 0;
     if (hp > 0) {
+        // H is read by the forward pass only and its gradient exists in the backward pass only:
+        // one buffer serves both, except for attention, whose backward pass reads H again
         w.h = take(M.n * hp);
-        w.gh = take(M.n * hp);
+        w.gh = c->model == GNN_GAT ? take(M.n * hp) : w.h;
         w.wpad = take(2 * din * hp);
     }
     if (c->model == GNN_GAT) {
@@ -1024,6 +1026,9 @@ gnn_status gnn_layer_bwd(gnn_ctx* c, int32_t layer, int32_t p, void* stream)
                     launch_fill_zero(c->gact[(size_t)layer - 2], c->M.n * (int64_t)c->dims[(size_t)layer - 1] * 4, s);
             }
             refresh_padded_weights(c, layer, s);
+            // grad H takes the buffer H was in
+            c->h_layer = 0;
+            std::fill(c->xf_fwd_done.begin(), c->xf_fwd_done.end(), 0);
             for (int32_t q = 0; q < c->M.k; ++q) c->xf_bwd_done[(size_t)(layer - 1) * (size_t)c->M.k + (size_t)q] = 0;
         }
         xf_aggregate_bwd(c, layer, p, s);

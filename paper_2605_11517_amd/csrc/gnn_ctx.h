@@ -81,10 +81,17 @@ struct gnn_ctx {
     bool transform_first(int32_t layer) const
     {
         if (model == GNN_GAT) return true;       // attention scores are taken from H = A W
-        if (order_mode != 1 || streaming() || dims[(size_t)layer] >= dims[(size_t)layer - 1]) return false;
-        // bfloat16 storage: only the output layer (its result is fp32 anyway), and only when its
-        // rows are whole 16-byte vectors
-        return !bf16() || (layer == L && dims[(size_t)layer] % 8 == 0);
+        if (order_mode != 1 || streaming()) return false;
+        const int64_t din = dims[(size_t)layer - 1], dout = dims[(size_t)layer];
+        if (bf16())
+            // bfloat16 storage: only the output layer (its result is fp32 anyway), and only when
+            // its rows are whole 16-byte vectors
+            return layer == L && dout < din && dout % 8 == 0;
+        // Rows moved per vertex and edge: aggregating first reads rows of the input width in the
+        // forward pass, again in the recompute, and writes them in the transposed pass (layers
+        // >= 2); transforming first aggregates once forward and once transposed, at the output
+        // width, and regathers nothing.
+        return 2 * dout < din * (layer >= 2 ? 3 : 2);
     }
     // width of H rows: d_layer rounded up to whole 16-byte vectors
     int32_t padded(int32_t layer) const { return (dims[(size_t)layer] + 3) / 4 * 4; }
