@@ -553,11 +553,11 @@ static void xf_aggregate_bwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s
                            (float*)(c->scratch + c->ws.partial), s);
         }
         if (layer >= 2) {
-            // self term: grad A^{l-1}_own += dY W_s^T, contracted over the padded width
+            // self term: grad A^{l-1}_own = dY W_s^T (the first thing written to these rows),
+            // contracted over the padded width
             const PaddedW ws = padded_weight(c, layer, 1);
             Timed t(c, s, GNN_K_GEMM_DZ);
             GemmEpilogue ep;
-            ep.accumulate = 1;
             launch_gemm_nt(dYp, dp, ws.p, ws.ld, c->gact[(size_t)layer - 2] + r0 * din, din, np, din, dp, ep, s);
         }
     }
@@ -954,7 +954,7 @@ gnn_status gnn_layer_transform_bwd(gnn_ctx* c, int32_t layer, int32_t p, void* s
         const PaddedW w = padded_weight(c, layer, 0);
         Timed t(c, s, GNN_K_GEMM_DZ);
         GemmEpilogue ep;
-        ep.accumulate = 1;
+        ep.accumulate = c->model == GNN_SAGE_MEAN ? 1 : 0;    // SAGE: the self term is there already
         launch_gemm_nt(gH, dp, w.p, w.ld, c->gact[(size_t)layer - 2] + r0 * din, din, np, din, dp, ep, s);
     }
     c->xf_bwd_done[(size_t)(layer - 1) * (size_t)M.k + (size_t)p] = 1;
@@ -1022,7 +1022,10 @@ gnn_status gnn_layer_bwd(gnn_ctx* c, int32_t layer, int32_t p, void* stream)
             {
                 Timed t(c, s, GNN_K_OTHER);
                 launch_fill_zero(c->scratch + c->ws.gh, c->M.n * (int64_t)c->padded(layer) * 4, s);
-                if (layer >= 2)
+                // grad A^{l-1} needs no initialisation here: each of its rows is written once (by
+                // the self term, else by grad H W^T) before anything is added to it; only the
+                // bfloat16 variant adds from the start
+                if (layer >= 2 && c->bf16())
                     launch_fill_zero(c->gact[(size_t)layer - 2], c->M.n * (int64_t)c->dims[(size_t)layer - 1] * 4, s);
             }
             refresh_padded_weights(c, layer, s);

@@ -37,7 +37,10 @@ def test_mid_workload_full_size(capsys):
     w = glorot_weights(dims, cfg["seed"], sage=True, bias_scale=0.05)
     say("inputs ready: n=%d entries=%d" % (n, rowptr[-1]))
 
-    s = Session("sage", dims, rowptr, colidx, cfg["k"], cfg["part"], cfg["seed"], X, w, y, m)
+    # the configuration bench.py times: switching-aware partitions, layer order by rows moved
+    s = Session("sage", dims, rowptr, colidx, cfg["k"], cfg["part"], cfg["seed"], X, w, y, m,
+                layer_order="auto")
+    assert [s.ctx.layer_is_transform_first(l) for l in (1, 2, 3)] == [False, True, True]
     loss = s.epoch()
     loss2 = s.epoch()
     assert loss == loss2
