@@ -18,7 +18,10 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int kThreads = 256;
 constexpr int BK = 16;
-constexpr int PF = 1;   // tiles of global loads in flight per thread
+constexpr int PF = 1;   // stages of global loads in flight per thread
+constexpr int SUB = 1;  // k-tiles of BK per LDS stage (one barrier per stage); 2 measured slower:
+                        // the forward contraction loses more to the larger LDS footprint than
+                        // the halved barrier count gains
 constexpr int PAD = 4;
 
 struct Operand {         // a matrix operand restricted to one K segment
@@ -181,8 +184,8 @@ __global__ __launch_bounds__(kThreads) void k_gemm(const GemmArgs g)
     constexpr int TM = WM / 32, TN = WN / 32; // 32x32 MFMA tiles per wave
     constexpr int A_TILE = A_KFAST ? BM * KF_LD : BK * (BM + PAD);
     constexpr int B_TILE = B_KFAST ? BN * KF_LD : BK * (BN + PAD);
-    __shared__ __attribute__((aligned(16))) float As[2][A_TILE];
-    __shared__ __attribute__((aligned(16))) float Bs[2][B_TILE];
+    __shared__ __attribute__((aligned(16))) float As[2][SUB * A_TILE];
+    __shared__ __attribute__((aligned(16))) float Bs[2][SUB * B_TILE];
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -198,8 +201,10 @@ __global__ __launch_bounds__(kThreads) void k_gemm(const GemmArgs g)
         kend0 = kbeg + g.split_chunk < kend0 ? kbeg + g.split_chunk : kend0;
         cbase += (int64_t)blockIdx.z * g.split_stride;
     }
-    const int64_t tiles0 = kend0 > kbeg ? (kend0 - kbeg + BK - 1) / BK : 0;
-    const int64_t tiles1 = (g.kseg[1] + BK - 1) / BK;
+    // a stage is SUB consecutive k-tiles of one segment (tiles past the segment's end are zero)
+    constexpr int SK = BK * SUB;
+    const int64_t tiles0 = kend0 > kbeg ? (kend0 - kbeg + SK - 1) / SK : 0;
+    const int64_t tiles1 = (g.kseg[1] + SK - 1) / SK;
     const int64_t ntiles = tiles0 + tiles1;
 
     floatx16 acc[TM][TN];
@@ -213,29 +218,41 @@ __global__ __launch_bounds__(kThreads) void k_gemm(const GemmArgs g)
     // Register ring of PF tiles: the global loads of tile t + PF are issued while tile t is
     // multiplied, so that a load has PF tile-times to arrive (one tile-time is far shorter than
     // the memory latency, above all with the fast bf16 MFMA).
-    float4 ra[PF][BM / 64], rb[PF][BN / 64];
-    auto load_tile = [&](int64_t t, float4 (&ra)[BM / 64], float4 (&rb)[BN / 64]) {
+    float4 ra[PF][SUB][BM / 64], rb[PF][SUB][BN / 64];
+    auto load_tile = [&](int64_t t, float4 (&ra)[SUB][BM / 64], float4 (&rb)[SUB][BN / 64]) {
         const int seg = t < tiles0 ? 0 : 1;
-        const int64_t k0 = seg == 0 ? kbeg + t * BK : (t - tiles0) * BK;
+        const int64_t ks = seg == 0 ? kbeg + t * SK : (t - tiles0) * SK;
         const int64_t kend = seg == 0 ? kend0 : (int64_t)g.kseg[1];
-        if (A_KFAST) load_kfast<BM, VEC_A>(g.a[seg].p, g.a[seg].ld, m0, g.m, (int32_t)k0, (int32_t)kend, ra);
-        else load_kslow<BM, VEC_A>(g.a[seg].p, g.a[seg].ld, k0, kend, m0, g.m, ra);
-        if (B_KFAST) load_kfast<BN, VEC_B>(g.b[seg].p, g.b[seg].ld, n0, g.n, (int32_t)k0, (int32_t)kend, rb);
-        else load_kslow<BN, VEC_B>(g.b[seg].p, g.b[seg].ld, k0, kend, n0, g.n, rb);
+#pragma unroll
+        for (int u = 0; u < SUB; ++u) {
+            // a tile wholly past the end is fetched from the segment's first tile and zeroed later
+            const int64_t k0 = ks + u * BK < kend ? ks + u * BK : ks;
+            if (A_KFAST) load_kfast<BM, VEC_A>(g.a[seg].p, g.a[seg].ld, m0, g.m, (int32_t)k0, (int32_t)kend, ra[u]);
+            else load_kslow<BM, VEC_A>(g.a[seg].p, g.a[seg].ld, k0, kend, m0, g.m, ra[u]);
+            if (B_KFAST) load_kfast<BN, VEC_B>(g.b[seg].p, g.b[seg].ld, n0, g.n, (int32_t)k0, (int32_t)kend, rb[u]);
+            else load_kslow<BN, VEC_B>(g.b[seg].p, g.b[seg].ld, k0, kend, n0, g.n, rb[u]);
+        }
     };
-    auto store_tile = [&](int buf, int64_t t, const float4 (&ra_in)[BM / 64], const float4 (&rb_in)[BN / 64]) {
+    auto store_tile = [&](int buf, int64_t t, const float4 (&ra_in)[SUB][BM / 64],
+                          const float4 (&rb_in)[SUB][BN / 64]) {
         const int seg = t < tiles0 ? 0 : 1;
-        const int64_t k0 = seg == 0 ? kbeg + t * BK : (t - tiles0) * BK;
+        const int64_t ks = seg == 0 ? kbeg + t * SK : (t - tiles0) * SK;
         const int64_t kend = seg == 0 ? kend0 : (int64_t)g.kseg[1];
-        float4 ra[BM / 64], rb[BN / 64];
 #pragma unroll
-        for (int i = 0; i < BM / 64; ++i) ra[i] = ra_in[i];
+        for (int u = 0; u < SUB; ++u) {
+            const bool live = ks + u * BK < kend;
+            const int64_t k0 = live ? ks + u * BK : ks;
+            const int64_t ke = live ? kend : ks;        // an empty range zeroes the whole tile
+            float4 ra[BM / 64], rb[BN / 64];
 #pragma unroll
-        for (int i = 0; i < BN / 64; ++i) rb[i] = rb_in[i];
-        if (A_KFAST) { mask_kfast<BM>(m0, g.m, k0, kend, ra); store_kfast<BM>(As[buf], ra); }
-        else { mask_kslow<BM>(k0, kend, m0, g.m, ra); store_kslow<BM>(As[buf], ra); }
-        if (B_KFAST) { mask_kfast<BN>(n0, g.n, k0, kend, rb); store_kfast<BN>(Bs[buf], rb); }
-        else { mask_kslow<BN>(k0, kend, n0, g.n, rb); store_kslow<BN>(Bs[buf], rb); }
+            for (int i = 0; i < BM / 64; ++i) ra[i] = ra_in[u][i];
+#pragma unroll
+            for (int i = 0; i < BN / 64; ++i) rb[i] = rb_in[u][i];
+            if (A_KFAST) { mask_kfast<BM>(m0, g.m, k0, ke, ra); store_kfast<BM>(As[buf] + u * A_TILE, ra); }
+            else { mask_kslow<BM>(k0, ke, m0, g.m, ra); store_kslow<BM>(As[buf] + u * A_TILE, ra); }
+            if (B_KFAST) { mask_kfast<BN>(n0, g.n, k0, ke, rb); store_kfast<BN>(Bs[buf] + u * B_TILE, rb); }
+            else { mask_kslow<BN>(k0, ke, n0, g.n, rb); store_kslow<BN>(Bs[buf] + u * B_TILE, rb); }
+        }
     };
 
 #pragma unroll
@@ -249,22 +266,27 @@ __global__ __launch_bounds__(kThreads) void k_gemm(const GemmArgs g)
             const int64_t t = t0 + dd;
             if (t >= ntiles) break;
             const int buf = (int)(t & 1);
-            // slot dd held tile t, already in LDS; past the end the last tile is fetched again
+            // slot dd held stage t, already in LDS; past the end the last stage is fetched again
             // (never used) so that the load stream has no branches
             load_tile(t + PF < ntiles ? t + PF : ntiles - 1, ra[dd], rb[dd]);
-        const int half = lane >> 5, xl = lane & 31;
-        float af[TM][8], bf[TN][8];
+            const int half = lane >> 5, xl = lane & 31;
 #pragma unroll
-        for (int i = 0; i < TM; ++i) load_fragment<BM, A_KFAST>(As[buf], wm0 + 32 * i + xl, half, af[i]);
+            for (int u = 0; u < SUB; ++u) {
+                float af[TM][8], bf[TN][8];
 #pragma unroll
-        for (int j = 0; j < TN; ++j) load_fragment<BN, B_KFAST>(Bs[buf], wn0 + 32 * j + xl, half, bf[j]);
-#pragma unroll
-        for (int st = 0; st < 8; ++st)
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
+                for (int i = 0; i < TM; ++i)
+                    load_fragment<BM, A_KFAST>(As[buf] + u * A_TILE, wm0 + 32 * i + xl, half, af[i]);
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i][st], bf[j][st], acc[i][j], 0, 0, 0);
+                    load_fragment<BN, B_KFAST>(Bs[buf] + u * B_TILE, wn0 + 32 * j + xl, half, bf[j]);
+#pragma unroll
+                for (int st = 0; st < 8; ++st)
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int j = 0; j < TN; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i][st], bf[j][st], acc[i][j], 0, 0, 0);
+            }
             if (t + 1 < ntiles) store_tile(buf ^ 1, t + 1, ra[(dd + 1) % PF], rb[(dd + 1) % PF]);
             __syncthreads();
         }
