@@ -354,7 +354,11 @@ __global__ __launch_bounds__(kBlock) void k_spmm_slots(const SpmmArgs g, int32_t
     const int lane = threadIdx.x % kWave;
     const int slot = lane / G, gl = lane % G;
     unsigned blk = blockIdx.x;
-    const int coff = (int)(blk % (unsigned)nslices) * (G * EPV) + gl * EPV;   // this lane's columns
+    // this lane's columns; lanes past the row end (rows narrower than G vectors) read column 0
+    // and store nothing
+    const int coff_raw = (int)(blk % (unsigned)nslices) * (G * EPV) + gl * EPV;
+    const bool live = coff_raw < g.d;
+    const int coff = live ? coff_raw : 0;
     blk /= (unsigned)nslices;
     const int64_t item = ((int64_t)blk * (kBlock / kWave) + threadIdx.x / kWave) * S + slot;
 
@@ -420,6 +424,7 @@ __global__ __launch_bounds__(kBlock) void k_spmm_slots(const SpmmArgs g, int32_t
             }
         }
     }
+    if (!live) return;
     if (item < g.it.nsegs) {
         float* o = g.partial + item * (int64_t)g.ld + coff;
 #pragma unroll
@@ -428,13 +433,20 @@ __global__ __launch_bounds__(kBlock) void k_spmm_slots(const SpmmArgs g, int32_t
                 make_float4(acc[4 * h], acc[4 * h + 1], acc[4 * h + 2], acc[4 * h + 3]);
     } else if (row >= 0) {
         const float sc = g.rowscale ? g.rowscale[row] : 1.f;
-        TOut* o = static_cast<TOut*>(g.out) + row * (int64_t)g.ld + coff;
+        TOut* o = static_cast<TOut*>(g.out) + g.out_row(row) * (int64_t)g.ld + coff;
         constexpr int OPV = Elem<TOut>::EPV;
+        const bool add = g.map_n_own >= 0;     // fused scatter-accumulate (fp32 output): one slot per row
 #pragma unroll
         for (int h = 0; h < EPV / OPV; ++h) {
             float f[OPV];
 #pragma unroll
             for (int i = 0; i < OPV; ++i) f[i] = sc * acc[h * OPV + i];
+            if (add) {
+                float old[OPV];
+                Elem<TOut>::unpack(*reinterpret_cast<const uint4*>(o + h * OPV), old);
+#pragma unroll
+                for (int i = 0; i < OPV; ++i) f[i] += old[i];
+            }
             *reinterpret_cast<uint4*>(o + h * OPV) = Elem<TOut>::pack(f);
         }
     }
@@ -579,10 +591,36 @@ void spmm_typed(const int64_t* rp, const int32_t* col, const float* w, const flo
             return;
         }
     }
+    const bool vec = (d % EPV == 0) && (d % Elem<TOut>::EPV == 0);
+    // Narrow rows (at most 512 bytes): the cost is latency per row, not bytes, above all in the
+    // transposed operator whose rows have a handful of entries.  The slot-per-item kernel without
+    // slicing works on 64 / G rows per wavefront at once instead of one after the other.
+    static const bool use_narrow = [] {
+        const char* e = std::getenv("GNNMI_SPMM_NARROW");
+        return !(e && e[0] == '0');
+    }();
+    const int nvec = (d + EPV - 1) / EPV;
+    if (use_narrow && vec && nvec <= 32 && items.rows_sorted && (sc.n_own < 0 || sizeof(TOut) == 4) &&
+        items.nsegs + items.nshort > 0) {
+        const int G = nvec <= 4 ? 4 : nvec <= 8 ? 8 : nvec <= 16 ? 16 : 32;
+        const int S = kWave / G;
+        const int64_t n_items = items.nsegs + items.nshort;
+        const int64_t blocks = (n_items + (int64_t)wpb * S - 1) / ((int64_t)wpb * S);
+        SpmmArgs g;
+        g.rp = rp; g.col = col; g.w = w; g.rowscale = rowscale;
+        g.a_rows = a_rows; g.n_a = n_a; g.b_rows = b_rows; g.out = out; g.d = d; g.ld = d;
+        g.it = items; g.partial = partial;
+        g.map_n_own = sc.n_own; g.map_base = sc.base_row; g.map_idx = sc.idx;
+        const dim3 grid1((unsigned)blocks);
+        if (G == 4) hipLaunchKernelGGL((k_spmm_slots<TIn, TOut, 4>), grid1, dim3(kBlock), 0, s, g, 1);
+        else if (G == 8) hipLaunchKernelGGL((k_spmm_slots<TIn, TOut, 8>), grid1, dim3(kBlock), 0, s, g, 1);
+        else if (G == 16) hipLaunchKernelGGL((k_spmm_slots<TIn, TOut, 16>), grid1, dim3(kBlock), 0, s, g, 1);
+        else hipLaunchKernelGGL((k_spmm_slots<TIn, TOut, 32>), grid1, dim3(kBlock), 0, s, g, 1);
+        return;
+    }
     const int64_t nitems = items.nsegs + items.nranges;
     const dim3 grid((unsigned)((nitems + wpb - 1) / wpb));
     const dim3 block(kBlock);
-    const bool vec = (d % EPV == 0) && (d % Elem<TOut>::EPV == 0);
     // rows wider than 256 vectors (1024 floats / 2048 bf16) are processed in column blocks
     constexpr int32_t kColBlock = 256 * EPV;
     for (int32_t c0 = 0; c0 < d; c0 += kColBlock) {
