@@ -552,9 +552,10 @@ static void xf_aggregate_bwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s
             launch_gemm_tn(in_own, din, dYp, dp, c->gw[(size_t)3 * (layer - 1) + 1], dout, din, dout, np,
                            (float*)(c->scratch + c->ws.partial), s);
         }
-        if (layer >= 2) {
+        if (layer >= 2 && layer < L) {
             // self term: grad A^{l-1}_own = dY W_s^T (the first thing written to these rows),
-            // contracted over the padded width
+            // contracted over the padded width.  The output layer has dY = grad A^L at hand in
+            // the second sweep as well and takes both terms of grad A^{l-1} in one contraction there.
             const PaddedW ws = padded_weight(c, layer, 1);
             Timed t(c, s, GNN_K_GEMM_DZ);
             GemmEpilogue ep;
@@ -950,7 +951,22 @@ gnn_status gnn_layer_transform_bwd(gnn_ctx* c, int32_t layer, int32_t p, void* s
         launch_gemm_tn(in_own, din, gH, dp, c->gw[(size_t)3 * (layer - 1)], dout, din, dout, np,
                        (float*)(c->scratch + c->ws.partial), s);
     }
-    if (layer >= 2) {
+    if (layer >= 2 && layer == c->L && c->model == GNN_SAGE_MEAN) {
+        // grad A^{l-1}_own = grad H_p W^T + dY_p W_s^T in one pass over the result (dY_p = grad A^L_p)
+        const float* dY = c->gact[(size_t)layer - 1] + r0 * dout;
+        if (dp != dout) {
+            Timed t(c, s, GNN_K_OTHER);
+            float* pad = (float*)(c->scratch + c->ws.dz);
+            launch_pad_rows(pad, dY, np, dout, dp, s);
+            dY = pad;
+        }
+        const PaddedW w = padded_weight(c, layer, 0), ws = padded_weight(c, layer, 1);
+        Timed t(c, s, GNN_K_GEMM_DZ);
+        GemmSeg seg[2];
+        seg[0].a = gH; seg[0].lda = dp; seg[0].b = w.p; seg[0].ldb = w.ld; seg[0].k = dp;
+        seg[1].a = dY; seg[1].lda = dp; seg[1].b = ws.p; seg[1].ldb = ws.ld; seg[1].k = dp;
+        launch_gemm_nt2(seg, 2, c->gact[(size_t)layer - 2] + r0 * din, din, np, din, GemmEpilogue{}, s);
+    } else if (layer >= 2) {
         const PaddedW w = padded_weight(c, layer, 0);
         Timed t(c, s, GNN_K_GEMM_DZ);
         GemmEpilogue ep;

@@ -147,6 +147,9 @@ void launch_gemm_nn(const GemmSeg* segs, int nseg, float* c, int64_t ldc, int64_
 void launch_gemm_nt(const float* a, int64_t lda, const float* b, int64_t ldb, float* c,
                     int64_t ldc, int64_t m, int32_t n, int32_t k, const GemmEpilogue& ep,
                     hipStream_t s);
+// C[M x N] = sum over segments A_seg[M x K_seg] * B_seg^T with B_seg stored [N x K_seg] row-major
+void launch_gemm_nt2(const GemmSeg* segs, int nseg, float* c, int64_t ldc, int64_t m, int32_t n,
+                     const GemmEpilogue& ep, hipStream_t s);
 // C[M x N] += A^T B with A stored [K x M], B stored [K x N] (K = number of vertices, large):
 // split over K into `splits` partial products in `partial`, then reduced in a fixed order.
 int gemm_tn_splits(int64_t kdim, int32_t m, int32_t n);

@@ -423,6 +423,21 @@ void launch_gemm_nt(const float* a, int64_t lda, const float* b, int64_t ldb, fl
     launch_gemm<true, true>(g, 1, s);
 }
 
+void launch_gemm_nt2(const GemmSeg* segs, int nseg, float* c, int64_t ldc, int64_t m, int32_t n,
+                     const GemmEpilogue& ep, hipStream_t s)
+{
+    GemmArgs g{};
+    for (int i = 0; i < 2; ++i) {
+        const GemmSeg& sg = segs[i < nseg ? i : 0];
+        g.a[i] = {sg.a, sg.lda};
+        g.b[i] = {sg.b, sg.ldb};
+        g.kseg[i] = i < nseg ? sg.k : 0;
+    }
+    g.c = c; g.ldc = ldc; g.m = m; g.n = n;
+    g.bias = ep.bias; g.relu = ep.relu; g.accumulate = ep.accumulate;
+    launch_gemm<true, true>(g, 1, s);
+}
+
 int gemm_tn_splits(int64_t kdim, int32_t m, int32_t n)
 {
     const int64_t tiles = (int64_t)((m + 127) / 128) * ((n + 127) / 128);
