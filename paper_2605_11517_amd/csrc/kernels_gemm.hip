@@ -18,7 +18,9 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int kThreads = 256;
 constexpr int BK = 16;
-constexpr int PF = 1;   // stages of global loads in flight per thread
+constexpr int PF = 1;   // stages of global loads in flight per thread; 2 and 3 measured slower, also on
+                        // the narrow (48-wide) contractions: those are bound by the MFMA work of
+                        // their padded 64-wide tile, not by loads in flight
 constexpr int SUB = 1;  // k-tiles of BK per LDS stage (one barrier per stage); 2 measured slower:
                         // the forward contraction loses more to the larger LDS footprint than
                         // the halved barrier count gains
@@ -60,19 +62,21 @@ __device__ inline void load_kfast(const float* __restrict__ p, int64_t ld, int64
         r[i] = v;
     }
 }
-// k-fast tiles are kept [x][k] in LDS (row stride BK + 4 floats): one 16-byte store per
-// register, and an MFMA lane later fetches eight consecutive k of its row with two 16-byte
-// reads.
-constexpr int KF_LD = 20;   // BK + 4
+// k-fast tiles are kept [x][k] in LDS: one 16-byte store per register, and an MFMA lane later
+// fetches eight consecutive k of its row with two 16-byte reads.  Rows are BK floats apart and
+// the four 16-byte chunks of row x are rotated by x / 4: sixteen consecutive lanes then touch
+// all 64 banks exactly once both when storing (4 rows x 4 chunks) and when reading (16 rows,
+// one chunk each); a padded row stride can satisfy only one of the two.
+constexpr int KF_LD = BK;
+__device__ inline int kf_chunk(int x, int chunk) { return 4 * ((chunk + (x >> 2)) & 3); }
 template <int BT>
 __device__ inline void store_kfast(float* S, const float4 (&r)[BT / 64])
 {
     const int t = threadIdx.x;
-    const int kq = (t & 3) * 4;
 #pragma unroll
     for (int i = 0; i < BT / 64; ++i) {
         const int x = (t >> 2) + 64 * i;
-        *reinterpret_cast<float4*>(S + x * KF_LD + kq) = r[i];
+        *reinterpret_cast<float4*>(S + x * KF_LD + kf_chunk(x, t & 3)) = r[i];
     }
 }
 
@@ -127,8 +131,8 @@ template <int BT, bool KFAST>
 __device__ inline void load_fragment(const float* S, int x, int half, float (&f)[8])
 {
     if (KFAST) {
-        const float4 lo = *reinterpret_cast<const float4*>(S + x * KF_LD + 8 * half);
-        const float4 hi = *reinterpret_cast<const float4*>(S + x * KF_LD + 8 * half + 4);
+        const float4 lo = *reinterpret_cast<const float4*>(S + x * KF_LD + kf_chunk(x, 2 * half));
+        const float4 hi = *reinterpret_cast<const float4*>(S + x * KF_LD + kf_chunk(x, 2 * half + 1));
         f[0] = lo.x; f[1] = lo.y; f[2] = lo.z; f[3] = lo.w;
         f[4] = hi.x; f[5] = hi.y; f[6] = hi.z; f[7] = hi.w;
     } else {
@@ -269,6 +273,9 @@ __global__ __launch_bounds__(kThreads) void k_gemm(const GemmArgs g)
             // slot dd held stage t, already in LDS; past the end the last stage is fetched again
             // (never used) so that the load stream has no branches
             load_tile(t + PF < ntiles ? t + PF : ntiles - 1, ra[dd], rb[dd]);
+            // keep the loads where they are: left alone, the scheduler sinks them below the
+            // MFMA block, right in front of the wait that precedes the LDS store
+            __builtin_amdgcn_sched_barrier(0);
             const int half = lane >> 5, xl = lane & 31;
 #pragma unroll
             for (int u = 0; u < SUB; ++u) {
