@@ -10,6 +10,7 @@
 // that are not multiples of 4 floats (e.g. 47 classes) take a scalar-load variant of the same
 // kernel; tails in M, N and K are zero-filled in LDS, never in memory.
 #include "gnn_internal.h"
+#include <cstdlib>
 
 namespace gnnmi {
 namespace {
@@ -177,7 +178,20 @@ struct GemmArgs {
     int32_t accumulate;
     int64_t split_chunk;     // K per split (multiple of BK); 0 = no split
     int64_t split_stride;    // elements between the partial C of consecutive splits
+    int32_t nt_1d;           // > 0: one-dimensional grid over (M tile, N tile), see tile_of_block
 };
+
+// Which tile a workgroup of a one-dimensional grid owns.  Workgroups are dealt to the 8 XCDs
+// round-robin, each XCD with its own L2: block b runs on XCD b % 8 as that XCD's (b / 8)-th
+// workgroup.  The workgroups of one XCD walk all N tiles of an M tile before the next M tile,
+// so the rows of A they share are fetched into that L2 once instead of once per N tile.
+__device__ inline bool tile_of_block(int64_t b, int64_t mt, int32_t nt, int64_t& mtile, int32_t& ntile)
+{
+    const int64_t slot = b >> 3;
+    ntile = (int32_t)(slot % nt);
+    mtile = (slot / nt) * 8 + (b & 7);
+    return mtile < mt;
+}
 
 // A_KFAST: A(m,k) = a[m*lda + k]   (else a[k*lda + m])
 // B_KFAST: B(k,n) = b[n*ldb + k]   (else b[k*ldb + n])
@@ -194,8 +208,11 @@ __global__ __launch_bounds__(kThreads) void k_gemm(const GemmArgs g)
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int wm0 = (wave >> 1) * WM, wn0 = (wave & 1) * WN;
-    const int64_t m0 = (int64_t)blockIdx.x * BM;
-    const int32_t n0 = blockIdx.y * BN;
+    int64_t mtile = blockIdx.x;
+    int32_t ntile = blockIdx.y;
+    if (g.nt_1d > 0 && !tile_of_block(blockIdx.x, (g.m + BM - 1) / BM, g.nt_1d, mtile, ntile)) return;
+    const int64_t m0 = mtile * BM;
+    const int32_t n0 = ntile * BN;
 
     // K range of this workgroup (split-K only with a single segment)
     int64_t kbeg = 0, kend0 = g.kseg[0];
@@ -375,11 +392,24 @@ void launch_gemm(const GemmArgs& g, int splits, hipStream_t s)
     // ld >= m (or n) floats long with ld a multiple of 4, so the last vector of a row stays inside
     // the row; what it reads past m (or n) only reaches columns of C that are never stored)
     const bool big_m = g.m > 64, big_n = g.n > 64;
+    static const bool xcd_map = [] {
+        const char* e = getenv("GNNMI_GEMM_XCD_MAP");
+        return !(e && e[0] == '0');
+    }();
 #define GNN_GEMM(BM, BN, VA, VB)                                                                \
-    hipLaunchKernelGGL((k_gemm<BM, BN, A_KFAST, B_KFAST, VA, VB>),                              \
-                       dim3((unsigned)((g.m + BM - 1) / BM), (unsigned)((g.n + BN - 1) / BN),   \
-                            (unsigned)splits),                                                  \
-                       dim3(kThreads), 0, s, g)
+    do {                                                                                        \
+        const int64_t mt = (g.m + BM - 1) / BM;                                                 \
+        const int32_t nt = (g.n + BN - 1) / BN;                                                 \
+        GemmArgs ga = g;                                                                        \
+        if (splits == 1 && nt > 1 && xcd_map) {                                                 \
+            ga.nt_1d = nt;                                                                      \
+            hipLaunchKernelGGL((k_gemm<BM, BN, A_KFAST, B_KFAST, VA, VB>),                      \
+                               dim3((unsigned)((mt + 7) / 8 * 8 * nt)), dim3(kThreads), 0, s, ga); \
+        } else {                                                                                \
+            hipLaunchKernelGGL((k_gemm<BM, BN, A_KFAST, B_KFAST, VA, VB>),                      \
+                               dim3((unsigned)mt, (unsigned)nt, (unsigned)splits), dim3(kThreads), 0, s, ga); \
+        }                                                                                       \
+    } while (0)
 #define GNN_GEMM_TILE(VA, VB)                                     \
     do {                                                          \
         if (big_m && big_n) GNN_GEMM(128, 128, VA, VB);           \

@@ -14,6 +14,7 @@
 // rows, which is conflict-free, whereas transposing on the way into LDS would put the sixteen
 // lanes of a k-row on one bank.
 #include "gnn_internal.h"
+#include <cstdlib>
 
 namespace gnnmi {
 namespace {
@@ -24,7 +25,8 @@ typedef uint16_t bf16_t;
 
 constexpr int kThreads = 256;
 constexpr int BK = 32;
-constexpr int PF = 1;         // tiles of global loads in flight per thread
+constexpr int PF = 1;         // tiles of global loads in flight per thread (2 and 3: occupancy falls
+                              // from 3 to 2 waves per SIMD, 20-30 % slower)
 constexpr int LDK = BK + 8;   // k-fast tiles: [row][k], row stride 80 bytes (conflict-free 16-byte reads)
 constexpr int XPAD = 4;       // k-slow tiles: [k][row], row stride BT + 4 elements
 
@@ -173,7 +175,20 @@ struct Args {
     const float* bias;
     int32_t relu, accumulate, out_bf16;
     int64_t split_chunk, split_stride;
+    int32_t nt_1d;           // > 0: one-dimensional grid over (M tile, N tile), see tile_of_block
 };
+
+// Which tile a workgroup of a one-dimensional grid owns.  Workgroups are dealt to the 8 XCDs
+// round-robin, each XCD with its own L2: block b runs on XCD b % 8 as that XCD's (b / 8)-th
+// workgroup.  The workgroups of one XCD walk all N tiles of an M tile before the next M tile,
+// so the rows of A they share are fetched into that L2 once instead of once per N tile.
+__device__ inline bool tile_of_block(int64_t b, int64_t mt, int32_t nt, int64_t& mtile, int32_t& ntile)
+{
+    const int64_t slot = b >> 3;
+    ntile = (int32_t)(slot % nt);
+    mtile = (slot / nt) * 8 + (b & 7);
+    return mtile < mt;
+}
 
 template <int BM, int BN, bool A_KFAST, bool B_KFAST, bool VEC_A, bool VEC_B>
 __global__ __launch_bounds__(kThreads) void k_gemm_bf16(const Args g)
@@ -188,8 +203,11 @@ __global__ __launch_bounds__(kThreads) void k_gemm_bf16(const Args g)
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int wm0 = (wave >> 1) * WM, wn0 = (wave & 1) * WN;
-    const int64_t m0 = (int64_t)blockIdx.x * BM;
-    const int32_t n0 = blockIdx.y * BN;
+    int64_t mtile = blockIdx.x;
+    int32_t ntile = blockIdx.y;
+    if (g.nt_1d > 0 && !tile_of_block(blockIdx.x, (g.m + BM - 1) / BM, g.nt_1d, mtile, ntile)) return;
+    const int64_t m0 = mtile * BM;
+    const int32_t n0 = ntile * BN;
 
     int64_t kbeg = 0, kend0 = g.kseg[0];
     int64_t coff = 0;
@@ -252,6 +270,9 @@ __global__ __launch_bounds__(kThreads) void k_gemm_bf16(const Args g)
             // slot dd held tile t, already in LDS; past the end the last tile is fetched again
             // (never used) so that the load stream has no branches
             load_tile(t + PF < ntiles ? t + PF : ntiles - 1, ra[dd], rb[dd]);
+            // keep the loads ahead of the MFMA block (the scheduler would sink them to the wait
+            // in front of the LDS store)
+            __builtin_amdgcn_sched_barrier(0);
         const int half = lane >> 5, xl = lane & 31;
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
@@ -314,11 +335,24 @@ void launch(const Args& g, int splits, hipStream_t s)
     if (!A_KFAST) va = va && g.m % 8 == 0;
     if (!B_KFAST) vb = vb && g.n % 8 == 0;
     const bool big_m = g.m > 64, big_n = g.n > 64;
+    static const bool xcd_map = [] {
+        const char* e = getenv("GNNMI_GEMM_XCD_MAP");
+        return !(e && e[0] == '0');
+    }();
 #define GNN_GEMM(BM, BN, VA, VB)                                                                \
-    hipLaunchKernelGGL((k_gemm_bf16<BM, BN, A_KFAST, B_KFAST, VA, VB>),                         \
-                       dim3((unsigned)((g.m + BM - 1) / BM), (unsigned)((g.n + BN - 1) / BN),   \
-                            (unsigned)splits),                                                  \
-                       dim3(kThreads), 0, s, g)
+    do {                                                                                        \
+        const int64_t mt = (g.m + BM - 1) / BM;                                                 \
+        const int32_t nt = (g.n + BN - 1) / BN;                                                 \
+        Args ga = g;                                                                            \
+        if (splits == 1 && nt > 1 && xcd_map) {                                                 \
+            ga.nt_1d = nt;                                                                      \
+            hipLaunchKernelGGL((k_gemm_bf16<BM, BN, A_KFAST, B_KFAST, VA, VB>),                 \
+                               dim3((unsigned)((mt + 7) / 8 * 8 * nt)), dim3(kThreads), 0, s, ga); \
+        } else {                                                                                \
+            hipLaunchKernelGGL((k_gemm_bf16<BM, BN, A_KFAST, B_KFAST, VA, VB>),                 \
+                               dim3((unsigned)mt, (unsigned)nt, (unsigned)splits), dim3(kThreads), 0, s, ga); \
+        }                                                                                       \
+    } while (0)
 #define GNN_GEMM_TILE(VA, VB)                                     \
     do {                                                          \
         if (big_m && big_n) GNN_GEMM(128, 128, VA, VB);           \
