@@ -134,6 +134,12 @@ void compute_workspace(gnn_ctx* c)
     w.losspart = take(loss_partial_floats(M.n, M.k));
     w.scalars = take(64);
     w.segpart = take(std::max(M.plan_fwd.max_segs, M.plan_bwd.max_segs) * din);
+    if (c->bf16()) {
+        int64_t wmax = 0;
+        for (int32_t l = 0; l < L; ++l)
+            wmax = std::max<int64_t>(wmax, (int64_t)c->dims[(size_t)l] * c->dims[(size_t)l + 1]);
+        w.wt = take((wmax + 1) / 2);
+    }
     int64_t hp = 0;
     for (int32_t l = 1; l <= L; ++l)
         if (c->transform_first(l)) hp = std::max<int64_t>(hp, c->padded(l));
@@ -281,7 +287,7 @@ void compute_fwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, char*
             seg[1].b = c->w[(size_t)3 * (layer - 1) + 1]; seg[1].ldb = dout; seg[1].k = din;
         }
         launch_gemm_bf16_nn(seg, sage ? 2 : 1, out_own, layer < c->L ? 1 : 0 /* logits stay fp32 */, dout,
-                            np, dout, ep, s);
+                            np, dout, ep, s, c->scratch + c->ws.wt);
     }
     if (c->dropout_p > 0.f && layer < c->L) {
         const uint64_t key = splitmix64(c->dropout_seed ^ splitmix64((uint64_t)(64 * c->dropout_epoch + layer)));
@@ -379,7 +385,7 @@ const char* compute_bwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own
 }
 
 void compute_bwd_self(gnn_ctx* c, int32_t layer, int32_t p, const char* dY, float* gprev_own,
-                      hipStream_t s)
+                      hipStream_t s, int accumulate)
 {
     if (c->model != GNN_SAGE_MEAN || layer < 2) return;
     const int64_t np = c->M.off[(size_t)p + 1] - c->M.off[(size_t)p];
@@ -387,7 +393,7 @@ void compute_bwd_self(gnn_ctx* c, int32_t layer, int32_t p, const char* dY, floa
     const char* Ws = c->w[(size_t)3 * (layer - 1) + 1];
     Timed t(c, s, GNN_K_GEMM_DZ);
     GemmEpilogue ep;
-    ep.accumulate = 1;
+    ep.accumulate = accumulate;
     if (c->bf16()) launch_gemm_bf16_nt(dY, dout, Ws, dout, gprev_own, 0, din, np, din, dout, ep, s);
     else launch_gemm_nt((const float*)dY, dout, (const float*)Ws, dout, gprev_own, din, np, din, dout, ep, s);
 }
@@ -505,7 +511,8 @@ static void xf_aggregate_bwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s
                                     dout, din, dout, np, (float*)(c->scratch + c->ws.partial), s);
             }
             if (layer >= 2)
-                compute_bwd_self(c, layer, p, (const char*)dYbuf, c->gact[(size_t)layer - 2] + r0 * din, s);
+                // (the first thing written to these rows of grad A^{l-1})
+                compute_bwd_self(c, layer, p, (const char*)dYbuf, c->gact[(size_t)layer - 2] + r0 * din, s, 0);
         }
         const int64_t t0b = M.toff[(size_t)p];
         const SpmmItems itb = plan_items(M.plan_bwd, c->D.bwd, p);
@@ -938,7 +945,7 @@ gnn_status gnn_layer_transform_bwd(gnn_ctx* c, int32_t layer, int32_t p, void* s
         if (layer >= 2) {
             Timed t(c, s, GNN_K_GEMM_DZ);
             GemmEpilogue ep;
-            ep.accumulate = 1;
+            ep.accumulate = c->model == GNN_SAGE_MEAN ? 1 : 0;    // SAGE: the self term is there already
             launch_gemm_bf16_nt(gHb, dp, c->w[(size_t)3 * (layer - 1)], dout, c->gact[(size_t)layer - 2] + r0 * din, 0,
                                 din, np, din, dout, ep, s);
         }
@@ -1039,10 +1046,7 @@ gnn_status gnn_layer_bwd(gnn_ctx* c, int32_t layer, int32_t p, void* stream)
                 Timed t(c, s, GNN_K_OTHER);
                 launch_fill_zero(c->scratch + c->ws.gh, c->M.n * (int64_t)c->padded(layer) * 4, s);
                 // grad A^{l-1} needs no initialisation here: each of its rows is written once (by
-                // the self term, else by grad H W^T) before anything is added to it; only the
-                // bfloat16 variant adds from the start
-                if (layer >= 2 && c->bf16())
-                    launch_fill_zero(c->gact[(size_t)layer - 2], c->M.n * (int64_t)c->dims[(size_t)layer - 1] * 4, s);
+                // the self term, else by grad H W^T) before anything is added to it
             }
             refresh_padded_weights(c, layer, s);
             // grad H takes the buffer H was in

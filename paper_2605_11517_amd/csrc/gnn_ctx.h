@@ -41,6 +41,7 @@ struct Workspace {  // byte offsets into `scratch`
             segpart = 0;
     int64_t h = 0, gh = 0;     // transform-first layers: H = A W and its gradient, n x padded width
     int64_t wpad = 0;          // and copies of W, W_s with rows padded to that width (2 x d_in x padded)
+    int64_t wt = 0;            // bfloat16 storage: room for one transposed weight matrix
     // graph attention: per-vertex scores and their gradients, staged boundary scores, per-entry
     // attention weights, edge-wise products, attention weights in transposed order
     int64_t ssrc = 0, sdst = 0, gssrc = 0, gsdst = 0, bs = 0, att = 0, dal = 0, twatt = 0;
@@ -184,7 +185,7 @@ const char* compute_bwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own
                         const char* act_own, float* fused_gprev, const SpmmScatter* fused_map, hipStream_t s);
 // SAGE self term: gprev_own (n_p x d_{l-1} fp32) += dY_p W_s^T
 void compute_bwd_self(gnn_ctx* c, int32_t layer, int32_t p, const char* dY, float* gprev_own,
-                      hipStream_t s);
+                      hipStream_t s, int accumulate = 1);
 
 void zero_weight_grads(gnn_ctx* c, hipStream_t s);
 SpmmItems plan_items(const HostMeta::Plan& H, const DevMeta::Plan& P, int32_t p);

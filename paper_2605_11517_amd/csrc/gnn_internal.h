@@ -165,8 +165,11 @@ struct GemmSegBf16 {
     int64_t ldb = 0;
     int32_t k = 0;
 };
+// bt_scratch: room for B^T (n x k bfloat16) when there is one segment; with it, large products
+// run as A (B^T)^T on the wide kernel for k-contiguous operands
 void launch_gemm_bf16_nn(const GemmSegBf16* segs, int nseg, void* c, int out_bf16, int64_t ldc,
-                         int64_t m, int32_t n, const GemmEpilogue& ep, hipStream_t s);
+                         int64_t m, int32_t n, const GemmEpilogue& ep, hipStream_t s,
+                         void* bt_scratch = nullptr);
 void launch_gemm_bf16_nt(const void* a, int64_t lda, const void* b, int64_t ldb, void* c,
                          int out_bf16, int64_t ldc, int64_t m, int32_t n, int32_t k,
                          const GemmEpilogue& ep, hipStream_t s);

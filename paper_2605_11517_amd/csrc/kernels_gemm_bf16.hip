@@ -368,6 +368,191 @@ void launch(const Args& g, int splits, hipStream_t s)
 #undef GNN_GEMM
 }
 
+// ---------------------------------------------------------------------------------------------
+// Wide variant for the large products with both operands k-contiguous (A [M x K], B [N x K]):
+// a 256 x 256 tile per workgroup of 8 wavefronts (2 x 4, 128 x 64 each), K in steps of 64.
+// The two LDS stages are filled by direct-to-LDS loads (global_load_lds_dwordx4: 16 bytes per
+// lane, a wavefront fills 1 KB of LDS per instruction, no registers and no ds_write involved),
+// issued for stage t + 1 right after the barrier that opens stage t.  Inside a tile row (128
+// bytes = eight 16-byte chunks) the chunks are permuted by the row number so that the sixteen
+// lanes of a fragment read touch every bank once; the permutation is applied on the global
+// side, by choosing which chunk a lane fetches.  bf16 results leave through LDS so that a lane
+// stores 16 contiguous bytes.
+constexpr int WBM = 256, WBN = 256, WBK = 64, WTHREADS = 512;
+constexpr int WROWB = WBK * 2;                         // bytes per tile row
+constexpr int WSTAGE = (WBM + WBN) * WROWB;            // bytes per stage
+constexpr int WTM = 128, WTN = 64;                     // wave tile
+constexpr int WCS = WTN * 2 + 16;                      // row stride of a wave's output patch, bytes
+constexpr int WLDS = 2 * WSTAGE > 8 * WTM * WCS ? 2 * WSTAGE : 8 * WTM * WCS;
+
+__device__ inline int wide_chunk(int x, int c) { return x * WROWB + ((c ^ ((x >> 1) & 7)) << 4); }
+
+__device__ inline void wide_issue(const bf16_t* __restrict__ p, int64_t ld, int64_t row0, int64_t nrows,
+                                  int64_t k0, char* lds_tile, int wave, int lane)
+{
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int q = j * 8 + wave;                    // block of 8 rows = 1 KB of LDS
+        const int row = q * 8 + (lane >> 3);
+        const int c = (lane & 7) ^ ((row >> 1) & 7);   // LDS slot lane & 7 of the row holds chunk c
+        int64_t gr = row0 + row;
+        gr = gr < nrows ? gr : nrows - 1;              // rows past the end: valid address, result unused
+        const bf16_t* src = p + gr * ld + k0 + c * 8;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                         (__attribute__((address_space(3))) void*)(lds_tile + q * 1024), 16, 0, 0);
+    }
+}
+
+// requires: one K segment, K a multiple of 64, 16-byte aligned rows of A and B
+__global__ __launch_bounds__(WTHREADS) void k_gemm_bf16_wide(const Args g)
+{
+    extern __shared__ __attribute__((aligned(1024))) char wlds[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave >> 2, wn = wave & 3;
+    int64_t mtile;
+    int32_t ntile;
+    if (!tile_of_block(blockIdx.x, (g.m + WBM - 1) / WBM, g.nt_1d, mtile, ntile)) return;
+    const int64_t m0 = mtile * WBM;
+    const int32_t n0 = ntile * WBN;
+    const int nstages = g.kseg[0] / WBK;
+
+    floatx16 acc[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    wide_issue(g.a[0], g.lda[0], m0, g.m, 0, wlds, wave, lane);
+    wide_issue(g.b[0], g.ldb[0], n0, g.n, 0, wlds + WBM * WROWB, wave, lane);
+    for (int t = 0; t < nstages; ++t) {
+        const int buf = t & 1;
+        __builtin_amdgcn_s_waitcnt(0x0F70);           // vmcnt(0): this thread's loads of stage t landed
+        __syncthreads();                               // everybody's did; stage t - 1 is no longer read
+        if (t + 1 < nstages) {
+            char* nxt = wlds + (buf ^ 1) * WSTAGE;
+            wide_issue(g.a[0], g.lda[0], m0, g.m, (int64_t)(t + 1) * WBK, nxt, wave, lane);
+            wide_issue(g.b[0], g.ldb[0], n0, g.n, (int64_t)(t + 1) * WBK, nxt + WBM * WROWB, wave, lane);
+        }
+        const char* As = wlds + buf * WSTAGE;
+        const char* Bs = As + WBM * WROWB;
+        const int xl = lane & 31, half = lane >> 5;
+#pragma unroll
+        for (int ks = 0; ks < WBK / 16; ++ks) {
+            bf16x8 av[4], bv[2];
+            const int c = 2 * ks + half;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                av[i] = *reinterpret_cast<const bf16x8*>(As + wide_chunk(wm * WTM + 32 * i + xl, c));
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                bv[j] = *reinterpret_cast<const bf16x8*>(Bs + wide_chunk(wn * WTN + 32 * j + xl, c));
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bv[j], acc[i][j], 0, 0, 0);
+        }
+    }
+
+    if (g.out_bf16) {
+        __syncthreads();                               // every wave is done reading the last stage
+        char* patch = wlds + (size_t)wave * WTM * WCS; // private to the wave: [128 rows][64 cols]
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int lc = 32 * j + (lane & 31);
+                const int32_t col = n0 + wn * WTN + lc;
+                const float bvl = (g.bias && col < g.n) ? g.bias[col] : 0.f;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int lr = 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                    float v = acc[i][j][r] + bvl;
+                    if (g.relu) v = v > 0.f ? v : 0.f;
+                    *reinterpret_cast<bf16_t*>(patch + lr * WCS + lc * 2) = (bf16_t)float_to_bf16(v);
+                }
+            }
+        // no barrier: the LDS accesses of one wave complete in order
+        const int cq = lane & 7, rr = lane >> 3;       // 8 lanes per row, 8 rows per pass
+        const int32_t col0 = n0 + wn * WTN + cq * 8;
+#pragma unroll
+        for (int ps = 0; ps < WTM / 8; ++ps) {
+            const int lr = ps * 8 + rr;
+            const int64_t row = m0 + wm * WTM + lr;
+            const uint4 v = *reinterpret_cast<const uint4*>(patch + lr * WCS + cq * 16);
+            if (row < g.m && col0 + 7 < g.n) {
+                *reinterpret_cast<uint4*>(static_cast<bf16_t*>(g.c) + row * g.ldc + col0) = v;
+            } else if (row < g.m) {
+                const bf16_t* e = reinterpret_cast<const bf16_t*>(&v);
+                for (int u = 0; u < 8; ++u)
+                    if (col0 + u < g.n) static_cast<bf16_t*>(g.c)[row * g.ldc + col0 + u] = e[u];
+            }
+        }
+        return;
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int32_t col = n0 + wn * WTN + 32 * j + (lane & 31);
+            if (col >= g.n) continue;
+            const float bvl = g.bias ? g.bias[col] : 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int64_t row = m0 + wm * WTM + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                if (row >= g.m) continue;
+                float v = acc[i][j][r] + bvl;
+                if (g.relu) v = v > 0.f ? v : 0.f;
+                float* dst = static_cast<float*>(g.c) + row * g.ldc + col;
+                if (g.accumulate) v += *dst;
+                *dst = v;
+            }
+        }
+}
+
+// Whether the wide kernel can take this product (both operands k-contiguous is the caller's business).
+bool wide_ok(const Args& g)
+{
+    static const bool enabled = [] {
+        const char* e = getenv("GNNMI_GEMM_WIDE");
+        return !(e && e[0] == '0');
+    }();
+    if (!enabled || g.kseg[1] != 0 || g.split_chunk != 0) return false;
+    if (g.m < 2 * WBM || g.n < WBN || g.kseg[0] < WBK || g.kseg[0] % WBK != 0) return false;
+    if (!aligned16(g.a[0]) || !aligned16(g.b[0]) || g.lda[0] % 8 != 0 || g.ldb[0] % 8 != 0) return false;
+    if (g.out_bf16 && (!aligned16(g.c) || g.ldc % 8 != 0)) return false;
+    return true;
+}
+
+bool launch_wide(const Args& g, hipStream_t s)
+{
+    static const bool attr_ok = hipFuncSetAttribute((const void*)k_gemm_bf16_wide,
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, WLDS) == hipSuccess;
+    if (!attr_ok) return false;
+    const int64_t mt = (g.m + WBM - 1) / WBM;
+    const int32_t nt = (g.n + WBN - 1) / WBN;
+    Args ga = g;
+    ga.nt_1d = nt;
+    hipLaunchKernelGGL(k_gemm_bf16_wide, dim3((unsigned)((mt + 7) / 8 * 8 * nt)), dim3(WTHREADS), WLDS, s, ga);
+    return true;
+}
+
+// dst [N x K] = src [K x N]^T, 32 x 32 tiles through LDS
+__global__ __launch_bounds__(256) void k_transpose_bf16(const bf16_t* __restrict__ src, int64_t ld, int32_t k,
+                                                        int32_t n, bf16_t* __restrict__ dst)
+{
+    __shared__ bf16_t tile[32][33];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;     // 32 x 8
+    const int32_t k0 = blockIdx.y * 32, n0 = blockIdx.x * 32;
+    for (int i = ty; i < 32; i += 8)
+        tile[i][tx] = (k0 + i < k && n0 + tx < n) ? src[(int64_t)(k0 + i) * ld + n0 + tx] : (bf16_t)0;
+    __syncthreads();
+    for (int i = ty; i < 32; i += 8)
+        if (n0 + i < n && k0 + tx < k) dst[(int64_t)(n0 + i) * k + k0 + tx] = tile[tx][i];
+}
+
 // dst[i] = bf16(src[i])
 __global__ __launch_bounds__(256) void k_to_bf16(const float* __restrict__ src, bf16_t* __restrict__ dst,
                                                  int64_t n)
@@ -379,8 +564,23 @@ __global__ __launch_bounds__(256) void k_to_bf16(const float* __restrict__ src, 
 }  // namespace
 
 void launch_gemm_bf16_nn(const GemmSegBf16* segs, int nseg, void* c, int out_bf16, int64_t ldc,
-                         int64_t m, int32_t n, const GemmEpilogue& ep, hipStream_t s)
+                         int64_t m, int32_t n, const GemmEpilogue& ep, hipStream_t s, void* bt_scratch)
 {
+    if (bt_scratch && nseg == 1) {
+        // large product: transpose B (the weights, small) and take the wide kernel
+        Args w{};
+        w.a[0] = w.a[1] = (const bf16_t*)segs[0].a; w.lda[0] = w.lda[1] = segs[0].lda;
+        w.b[0] = w.b[1] = (const bf16_t*)bt_scratch; w.ldb[0] = w.ldb[1] = segs[0].k;
+        w.kseg[0] = segs[0].k;
+        w.c = c; w.ldc = ldc; w.m = m; w.n = n; w.out_bf16 = out_bf16;
+        w.bias = ep.bias; w.relu = ep.relu; w.accumulate = ep.accumulate;
+        if (wide_ok(w)) {
+            hipLaunchKernelGGL(k_transpose_bf16, dim3((unsigned)((n + 31) / 32), (unsigned)((segs[0].k + 31) / 32)),
+                               dim3(256), 0, s, (const bf16_t*)segs[0].b, segs[0].ldb, segs[0].k, n,
+                               (bf16_t*)bt_scratch);
+            if (launch_wide(w, s)) return;
+        }
+    }
     Args g{};
     for (int i = 0; i < 2; ++i) {
         const GemmSegBf16& sg = segs[i < nseg ? i : 0];
@@ -403,6 +603,7 @@ void launch_gemm_bf16_nt(const void* a, int64_t lda, const void* b, int64_t ldb,
     g.kseg[0] = k; g.kseg[1] = 0;
     g.c = c; g.ldc = ldc; g.m = m; g.n = n; g.out_bf16 = out_bf16;
     g.bias = ep.bias; g.relu = ep.relu; g.accumulate = ep.accumulate;
+    if (wide_ok(g) && launch_wide(g, s)) return;
     launch<true, true>(g, 1, s);
 }
 

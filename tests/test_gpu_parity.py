@@ -219,6 +219,9 @@ BF16_CASES = [
     ("sage", (72, 136, 8), 2000, 16000, True, 3, "random"),        # ragged GEMM tiles
     ("gcn", (20, 50, 7), 500, 3000, False, 2, "random"),           # odd widths: scalar paths
     ("sage", (512, 1024, 64), 1500, 20000, True, 2, "lp"),         # the dense config's widths
+    # one-segment products large enough for the 256 x 256 tile kernel, with ragged row and
+    # column tiles (1500 rows per partition, 320 columns) and K = 128, 256 and 320
+    ("gcn", (128, 256, 320, 16), 3000, 30000, True, 2, "lp"),
 ]
 
 
