@@ -114,6 +114,8 @@ void compute_workspace(gnn_ctx* c)
         dout = std::max<int64_t>(dout, c->dims[(size_t)l + 1]);
         int sp = gemm_tn_splits(max_np, c->dims[(size_t)l], c->dims[(size_t)l + 1]);
         part = std::max(part, (int64_t)sp * c->dims[(size_t)l] * c->dims[(size_t)l + 1]);
+        if (c->bf16())
+            part = std::max(part, gemm_bf16_tn_partial_floats(max_np, c->dims[(size_t)l], c->dims[(size_t)l + 1]));
     }
     // rows that pass through staging, Z, the padded dY copy and the segment partial sums are as
     // wide as the widest aggregated row: an input width, or the padded output width of a layer

@@ -173,6 +173,8 @@ void launch_gemm_bf16_nn(const GemmSegBf16* segs, int nseg, void* c, int out_bf1
 void launch_gemm_bf16_nt(const void* a, int64_t lda, const void* b, int64_t ldb, void* c,
                          int out_bf16, int64_t ldc, int64_t m, int32_t n, int32_t k,
                          const GemmEpilogue& ep, hipStream_t s);
+// floats of `partial` a launch_gemm_bf16_tn of these dimensions may use
+int64_t gemm_bf16_tn_partial_floats(int64_t kdim, int32_t m, int32_t n);
 void launch_gemm_bf16_tn(const void* a, int64_t lda, const void* b, int64_t ldb, float* c,
                          int64_t ldc, int32_t m, int32_t n, int64_t kdim, float* partial,
                          hipStream_t s);

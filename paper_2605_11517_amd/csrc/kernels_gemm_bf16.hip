@@ -553,6 +553,155 @@ __global__ __launch_bounds__(256) void k_transpose_bf16(const bf16_t* __restrict
         if (n0 + i < n && k0 + tx < k) dst[(int64_t)(n0 + i) * k + k0 + tx] = tile[tx][i];
 }
 
+// ---------------------------------------------------------------------------------------------
+// Wide variant of the reduction over rows, C[m][n] = sum_k A[k][m] B[k][n] (grad W = Z^T dY):
+// the same 256 x 256 tile, 64 k-rows per stage and direct-to-LDS loads.  Both operands arrive
+// [k][m] (m contiguous), the MFMA wants eight consecutive k per lane: fragments are fetched
+// with the LDS transpose read (ds_read_b64_tr_b16).  Within a group of 16 lanes, lane j hands
+// in the address of four consecutive 16-bit elements, taken as row j / 4, columns
+// 4 (j % 4) .. + 3 of a 4 x 16 block, and lane i receives column i of that block - here rows
+// are k and columns are m, so a lane gets four consecutive k of its m; two reads make the
+// operand.  The 16-byte chunks of a k-row are permuted by the row number so that the four
+// k-rows of one read fall into different banks (applied on the global side, as above).
+// K is split over blockIdx.z into fp32 partial tiles, reduced afterwards in a fixed order.
+typedef short v4i16 __attribute__((ext_vector_type(4)));
+typedef short v8i16 __attribute__((ext_vector_type(8)));
+constexpr int TROWB = WBM * 2;                         // bytes per k-row of an operand tile
+constexpr int TOP = WBK * TROWB;                       // bytes per operand tile
+constexpr int TSTAGE = 2 * TOP;
+constexpr int TLDS = 2 * TSTAGE;
+
+struct ArgsT {
+    const bf16_t* a;
+    const bf16_t* b;
+    int64_t lda, ldb;
+    float* partial;            // [splits][m][n]
+    int32_t m, n;
+    int64_t k;                 // rows covered, a multiple of 64
+    int64_t chunk;             // rows per split, a multiple of 64
+};
+
+__device__ inline int tn_off(int k, int mcol)          // byte offset of element (k, mcol), mcol % 4 == 0
+{
+    return k * TROWB + ((((mcol >> 3) ^ ((k & 3) << 1)) << 4) | ((mcol & 4) << 1));
+}
+
+__device__ inline void tn_issue(const bf16_t* __restrict__ p, int64_t ld, int64_t krow0, int32_t col0,
+                                int32_t ncols, char* lds_tile, int wave, int lane)
+{
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int q = j * 8 + wave;                    // two k-rows = 1 KB of LDS
+        const int k = 2 * q + (lane >> 5);
+        const int mc = (lane & 31) ^ ((k & 3) << 1);
+        int32_t col = col0 + mc * 8;
+        col = col + 8 <= ncols ? col : 0;              // chunks past the end: valid address, result unused
+        const bf16_t* src = p + (krow0 + k) * ld + col;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                         (__attribute__((address_space(3))) void*)(lds_tile + q * 1024), 16, 0, 0);
+    }
+}
+
+// eight consecutive k (k8 .. k8 + 7) of this lane's row in the 32-column block starting at c0
+__device__ inline bf16x8 tn_fragment(const char* tile, int k8, int c0, int lane)
+{
+    const int j = lane & 15, grp = lane >> 4;
+    const int mcol = c0 + 16 * (grp & 1) + 4 * (j & 3);
+    const int k = k8 + (j >> 2);
+    const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (__attribute__((address_space(3))) v4i16*)(tile + tn_off(k, mcol)));
+    const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (__attribute__((address_space(3))) v4i16*)(tile + tn_off(k + 4, mcol)));
+    v8i16 r;
+    r[0] = lo[0]; r[1] = lo[1]; r[2] = lo[2]; r[3] = lo[3];
+    r[4] = hi[0]; r[5] = hi[1]; r[6] = hi[2]; r[7] = hi[3];
+    return __builtin_bit_cast(bf16x8, r);
+}
+
+// requires: m, n multiples of 8; rows of A and B 16-byte aligned; k and chunk multiples of 64
+__global__ __launch_bounds__(WTHREADS) void k_gemm_bf16_tn_wide(const ArgsT g)
+{
+    extern __shared__ __attribute__((aligned(1024))) char wlds[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave >> 2, wn = wave & 3;
+    const int32_t m0 = blockIdx.x * WBM, n0 = blockIdx.y * WBN;
+    const int64_t kbeg = (int64_t)blockIdx.z * g.chunk;
+    const int64_t kend = kbeg + g.chunk < g.k ? kbeg + g.chunk : g.k;
+    const int nstages = kend > kbeg ? (int)((kend - kbeg) / WBK) : 0;
+
+    floatx16 acc[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    if (nstages > 0) {
+        tn_issue(g.a, g.lda, kbeg, m0, g.m, wlds, wave, lane);
+        tn_issue(g.b, g.ldb, kbeg, n0, g.n, wlds + TOP, wave, lane);
+    }
+    for (int t = 0; t < nstages; ++t) {
+        const int buf = t & 1;
+        __builtin_amdgcn_s_waitcnt(0x0F70);           // vmcnt(0)
+        __syncthreads();
+        if (t + 1 < nstages) {
+            char* nxt = wlds + (buf ^ 1) * TSTAGE;
+            tn_issue(g.a, g.lda, kbeg + (int64_t)(t + 1) * WBK, m0, g.m, nxt, wave, lane);
+            tn_issue(g.b, g.ldb, kbeg + (int64_t)(t + 1) * WBK, n0, g.n, nxt + TOP, wave, lane);
+        }
+        const char* As = wlds + buf * TSTAGE;
+        const char* Bs = As + TOP;
+        const int khalf = (lane >> 5) * 8;
+#pragma unroll
+        for (int ks = 0; ks < WBK / 16; ++ks) {
+            bf16x8 av[4], bv[2];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) av[i] = tn_fragment(As, 16 * ks + khalf, wm * WTM + 32 * i, lane);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) bv[j] = tn_fragment(Bs, 16 * ks + khalf, wn * WTN + 32 * j, lane);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bv[j], acc[i][j], 0, 0, 0);
+        }
+    }
+    float* out = g.partial + (int64_t)blockIdx.z * g.m * g.n;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int32_t col = n0 + wn * WTN + 32 * j + (lane & 31);
+            if (col >= g.n) continue;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int32_t row = m0 + wm * WTM + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                if (row < g.m) out[(int64_t)row * g.n + col] = acc[i][j][r];
+            }
+        }
+}
+
+bool wide_tn_ok(const void* a, int64_t lda, const void* b, int64_t ldb, int32_t m, int32_t n, int64_t kdim)
+{
+    static const bool enabled = [] {
+        const char* e = getenv("GNNMI_GEMM_WIDE");
+        return !(e && e[0] == '0');
+    }();
+    return enabled && m >= WBM && n >= WBN && m % 8 == 0 && n % 8 == 0 && kdim >= 64 * WBK && aligned16(a) &&
+           aligned16(b) && lda % 8 == 0 && ldb % 8 == 0;
+}
+
+int wide_tn_splits(int64_t kdim, int32_t m, int32_t n)
+{
+    const int64_t tiles = (int64_t)((m + WBM - 1) / WBM) * ((n + WBN - 1) / WBN);
+    int64_t want = (512 + tiles - 1) / tiles;          // two workgroups per CU over the launch
+    const int64_t most = kdim / (16 * WBK);            // at least 16 stages per split
+    int64_t sp = want < most ? want : most;
+    sp = sp > 64 ? 64 : sp;
+    return (int)(sp < 1 ? 1 : sp);
+}
+
 // dst[i] = bf16(src[i])
 __global__ __launch_bounds__(256) void k_to_bf16(const float* __restrict__ src, bf16_t* __restrict__ dst,
                                                  int64_t n)
@@ -612,6 +761,27 @@ void launch_gemm_bf16_tn(const void* a, int64_t lda, const void* b, int64_t ldb,
                          hipStream_t s)
 {
     if (kdim <= 0 || m <= 0 || n <= 0) return;
+    if (wide_tn_ok(a, lda, b, ldb, m, n, kdim)) {
+        static const bool attr_ok = hipFuncSetAttribute((const void*)k_gemm_bf16_tn_wide,
+                                                        hipFuncAttributeMaxDynamicSharedMemorySize, TLDS) == hipSuccess;
+        if (attr_ok) {
+            // whole stages of 64 rows on the wide kernel, the last rows (fewer than 64) below
+            ArgsT w{};
+            w.a = (const bf16_t*)a; w.lda = lda; w.b = (const bf16_t*)b; w.ldb = ldb;
+            w.partial = partial; w.m = m; w.n = n;
+            w.k = kdim / WBK * WBK;
+            const int want = wide_tn_splits(kdim, m, n);
+            w.chunk = (w.k / WBK + want - 1) / want * WBK;
+            const int sp = (int)((w.k + w.chunk - 1) / w.chunk);
+            hipLaunchKernelGGL(k_gemm_bf16_tn_wide, dim3((unsigned)((m + WBM - 1) / WBM), (unsigned)((n + WBN - 1) / WBN),
+                                                         (unsigned)sp), dim3(WTHREADS), TLDS, s, w);
+            launch_reduce_partials(partial, sp, (int64_t)m * n, c, ldc, m, n, s);
+            if (w.k == kdim) return;
+            a = (const bf16_t*)a + w.k * lda;
+            b = (const bf16_t*)b + w.k * ldb;
+            kdim -= w.k;
+        }
+    }
     const int splits = gemm_tn_splits(kdim, m, n);
     int64_t chunk = (kdim + splits - 1) / splits;
     chunk = (chunk + BK - 1) / BK * BK;
@@ -624,6 +794,13 @@ void launch_gemm_bf16_tn(const void* a, int64_t lda, const void* b, int64_t ldb,
     g.split_stride = (int64_t)m * n;
     launch<false, false>(g, splits, s);
     launch_reduce_partials(partial, splits, (int64_t)m * n, c, ldc, m, n, s);
+}
+
+int64_t gemm_bf16_tn_partial_floats(int64_t kdim, int32_t m, int32_t n)
+{
+    const int64_t narrow = (int64_t)gemm_tn_splits(kdim, m, n) * m * n;
+    const int64_t wide = (int64_t)wide_tn_splits(kdim, m, n) * m * n;
+    return narrow > wide ? narrow : wide;
 }
 
 void launch_to_bf16(const float* src, void* dst, int64_t n, hipStream_t s)

@@ -222,6 +222,9 @@ BF16_CASES = [
     # one-segment products large enough for the 256 x 256 tile kernel, with ragged row and
     # column tiles (1500 rows per partition, 320 columns) and K = 128, 256 and 320
     ("gcn", (128, 256, 320, 16), 3000, 30000, True, 2, "lp"),
+    # 5000 rows per partition: the weight gradient's reduction over rows takes the 256 x 256 tile
+    # kernel for 78 whole stages of 64 rows and the narrow kernel for the last 8 rows
+    ("gcn", (256, 264, 16), 10000, 60000, True, 2, "random"),
 ]
 
 
