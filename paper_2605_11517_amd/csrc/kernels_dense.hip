@@ -107,27 +107,55 @@ __global__ __launch_bounds__(kBlock) void k_loss_finish(const float* __restrict_
 }
 
 // dy = scale * g * [act > 0] (act == null: dy aliases g, nothing is written) and per-block column
-// sums of dy into partial[block][d].  A block covers 64 rows; thread t walks columns
-// t, t + 256, ... so that a row segment is read coalesced.
+// sums of dy into partial[block][d].  A block covers 256 rows.  Up to 256 columns are handled at
+// a time: the block's threads form 256 / width row groups that walk the rows together (four
+// rows in flight per thread), and the groups are combined through LDS in a fixed order.
 __global__ __launch_bounds__(kBlock) void k_act_bwd(const float* __restrict__ g,
                                                     const float* __restrict__ act,
                                                     float* __restrict__ dy, int64_t rows,
                                                     int32_t d, float* __restrict__ partial,
                                                     float scale)
 {
+    __shared__ float sm[kBlock];
     const int64_t r0 = (int64_t)blockIdx.x * kRowsPerBlockAct;
     const int64_t r1 = r0 + kRowsPerBlockAct < rows ? r0 + kRowsPerBlockAct : rows;
-    for (int32_t c = threadIdx.x; c < d; c += kBlock) {
+    for (int32_t cc = 0; cc < d; cc += kBlock) {
+        const int cwe = d - cc < kBlock ? d - cc : kBlock;     // columns in this chunk
+        const int rpp = kBlock / cwe;                          // rows per pass
+        const int rsub = threadIdx.x / cwe;
+        const int32_t c = cc + threadIdx.x % cwe;
         float s = 0.f;
-        for (int64_t r = r0; r < r1; ++r) {
-            float v = g[r * d + c];
-            if (act) {
-                v = act[r * d + c] > 0.f ? v * scale : 0.f;
-                dy[r * d + c] = v;
+        if (rsub < rpp) {
+            constexpr int U = 4;
+            for (int64_t r = r0 + rsub; r < r1; r += (int64_t)rpp * U) {
+                float gv[U], av[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int64_t rr = r + (int64_t)u * rpp;
+                    const bool ok = rr < r1;
+                    gv[u] = ok ? g[rr * d + c] : 0.f;
+                    av[u] = (ok && act) ? act[rr * d + c] : 0.f;
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int64_t rr = r + (int64_t)u * rpp;
+                    float v = gv[u];
+                    if (act) {
+                        v = av[u] > 0.f ? v * scale : 0.f;
+                        if (rr < r1) dy[rr * d + c] = v;
+                    }
+                    s += v;
+                }
             }
-            s += v;
         }
-        partial[(int64_t)blockIdx.x * d + c] = s;
+        sm[threadIdx.x] = s;
+        __syncthreads();
+        if (threadIdx.x < cwe) {
+            float total = 0.f;
+            for (int q = 0; q < rpp; ++q) total += sm[q * cwe + threadIdx.x];
+            partial[(int64_t)blockIdx.x * d + c] = total;
+        }
+        __syncthreads();
     }
 }
 
