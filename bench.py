@@ -44,14 +44,16 @@ def algorithmic_bytes(stats, dims, model, n_parts, es=4, fused_scatter=False, xf
     xf = xf or [False] * L
     for l in range(1, L + 1):
         if xf[l - 1]:
-            row = (dims[l] + 3) // 4 * 4 * 4
-            one_gather = 2 * sum_b * row + 4 * sum_b
-            one_spmm = per_entry * nnz + 8 * (n + k) + sum_r * row + n * row + (4 * n if model == "sage" else 0)
+            wp = (dims[l] + 3) // 4 * 4
+            row = wp * 4                         # aggregated sums and gradients of H: fp32
+            hrow = wp * es                       # rows of H (and of dY) in the storage type
+            one_gather = 2 * sum_b * hrow + 4 * sum_b
+            one_spmm = per_entry * nnz + 8 * (n + k) + sum_r * hrow + n * row + (4 * n if model == "sage" else 0)
             # graph attention regathers, and reads every needed row once more for the edge-wise
             # products dY[v] . H[u] (same traffic as an aggregation, 4 bytes written per entry)
             out["gather"] += one_gather * (2 if model == "gat" else 1)
             out["spmm"] += one_spmm * (2 if model == "gat" else 1)
-            out["spmm_t"] += 8 * nnz + 8 * (sum_r + k) + n * row + 2 * sum_r * row + 4 * sum_b
+            out["spmm_t"] += 8 * nnz + 8 * (sum_r + k) + n * hrow + 2 * sum_r * row + 4 * sum_b
             continue
         d = dims[l - 1]
         row = d * es

@@ -476,13 +476,17 @@ static void xf_aggregate_fwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s
         ep.bias = bias;
         launch_gemm_nn(&seg, 1, out, dout, np, dout, ep, s);
         launch_add_padded(out, Z, np, dout, dp, nullptr, 1, relu, s);
+    } else if (b16 && layer < c->L) {
+        // hidden layer with bfloat16 storage: the output rows are rounded once, here
+        launch_bias_act_bf16(c->act[(size_t)layer - 1] + r0 * (int64_t)dout * 2, Z, np, dout, dp, bias, relu, s);
     } else {
         launch_add_padded(out, Z, np, dout, dp, bias, 0, relu, s);
     }
     if (c->dropout_p > 0.f && layer < c->L) {
         const uint64_t key = splitmix64(c->dropout_seed ^ splitmix64((uint64_t)(64 * c->dropout_epoch + layer)));
         const uint32_t threshold = (uint32_t)std::floor((double)c->dropout_p * 4294967296.0);
-        launch_dropout(out, 0, c->D.order + r0, np, dout, key, threshold, 1.f / (1.f - c->dropout_p), s);
+        launch_dropout(c->act[(size_t)layer - 1] + r0 * (int64_t)dout * c->act_es(layer), b16 ? 1 : 0,
+                       c->D.order + r0, np, dout, key, threshold, 1.f / (1.f - c->dropout_p), s);
     }
 }
 
@@ -504,7 +508,8 @@ static void xf_aggregate_bwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s
         // output layer with bfloat16 storage (dp == dout): dY as bfloat16, the rest as below
         {
             Timed t(c, s, GNN_K_ACT_BWD);
-            launch_act_bwd_bf16(g_own, nullptr, dYbuf, np, dout, gb, colpart, 1.f, s);
+            const char* act_own = layer < L ? c->act[(size_t)layer - 1] + r0 * (int64_t)dout * 2 : nullptr;
+            launch_act_bwd_bf16(g_own, act_own, dYbuf, np, dout, gb, colpart, layer < L ? drop_scale : 1.f, s);
         }
         if (c->model == GNN_SAGE_MEAN) {
             {
@@ -895,7 +900,8 @@ gnn_status gnn_layer_transform_fwd(gnn_ctx* c, int32_t layer, int32_t p, void* s
         GemmSegBf16 seg;
         seg.a = c->layer_input(layer, r0); seg.lda = din;
         seg.b = c->w[(size_t)3 * (layer - 1)]; seg.ldb = dout; seg.k = din;
-        launch_gemm_bf16_nn(&seg, 1, c->scratch + c->ws.h + r0 * dp * 2, 1, dp, np, dout, GemmEpilogue{}, s);
+        launch_gemm_bf16_nn(&seg, 1, c->scratch + c->ws.h + r0 * dp * 2, 1, dp, np, dout, GemmEpilogue{}, s,
+                            c->scratch + c->ws.wt);
         c->xf_fwd_done[(size_t)(layer - 1) * (size_t)M.k + (size_t)p] = 1;
         return check_launch(c, "gnn_layer_transform_fwd");
     }

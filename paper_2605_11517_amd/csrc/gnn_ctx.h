@@ -84,10 +84,9 @@ struct gnn_ctx {
         if (model == GNN_GAT) return true;       // attention scores are taken from H = A W
         if (order_mode != 1 || streaming()) return false;
         const int64_t din = dims[(size_t)layer - 1], dout = dims[(size_t)layer];
-        if (bf16())
-            // bfloat16 storage: only the output layer (its result is fp32 anyway), and only when
-            // its rows are whole 16-byte vectors
-            return layer == L && dout < din && dout % 8 == 0;
+        // bfloat16 storage: rows of H must be whole 16-byte vectors; a hidden layer's self term
+        // (GraphSAGE) would need an fp32 copy of its output rows, so there only the output layer
+        if (bf16() && (dout % 8 != 0 || (layer < L && model != GNN_GCN))) return false;
         // Rows moved per vertex and edge: aggregating first reads rows of the input width in the
         // forward pass, again in the recompute, and writes them in the transposed pass (layers
         // >= 2); transforming first aggregates once forward and once transposed, at the output

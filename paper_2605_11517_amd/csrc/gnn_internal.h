@@ -254,6 +254,9 @@ void launch_colsum_finish(const float* partial, int64_t nblocks, int32_t d, floa
 // z's row stride ldz >= d; and a row copy into a wider, zero-padded row.
 void launch_add_padded(float* out, const float* z, int64_t rows, int32_t d, int32_t ldz,
                        const float* bias, int accumulate, int relu, hipStream_t s);
+// out[i, :] = bfloat16(act(z[i, 0..d) + bias)), z fp32 with row stride ldz
+void launch_bias_act_bf16(void* out, const float* z, int64_t rows, int32_t d, int32_t ldz, const float* bias,
+                          int relu, hipStream_t s);
 void launch_pad_rows(float* dst, const float* src, int64_t rows, int32_t d, int32_t ld, hipStream_t s);
 
 // Training pieces: dropout on a block of activation rows (orig_of_row[r] = original vertex id

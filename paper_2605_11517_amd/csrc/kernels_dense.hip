@@ -339,6 +339,24 @@ __global__ __launch_bounds__(kBlock) void k_add_padded(float* __restrict__ out, 
     }
 }
 
+// out[i, j] = bf16(act(z[i, j] + bias[j])): z fp32 with row stride ldz, out bfloat16 with row stride d
+__global__ __launch_bounds__(kBlock) void k_bias_act_bf16(uint16_t* __restrict__ out, const float* __restrict__ z,
+                                                          int64_t rows, int32_t d, int32_t ldz,
+                                                          const float* __restrict__ bias, int relu)
+{
+    const int64_t total = rows * d;
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < total;
+         i += (int64_t)gridDim.x * kBlock) {
+        const int64_t r = i / d;
+        const int32_t j = (int32_t)(i - r * d);
+        float v = z[r * ldz + j];
+        if (bias) v += bias[j];
+        if (relu) v = v > 0.f ? v : 0.f;
+        const uint32_t u = __float_as_uint(v);
+        out[i] = (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+    }
+}
+
 // dst[r, 0..ld) = src[r, 0..d) followed by zeros (ld >= d)
 __global__ __launch_bounds__(kBlock) void k_pad_rows(float* __restrict__ dst, const float* __restrict__ src,
                                                      int64_t rows, int32_t d, int32_t ld)
@@ -485,6 +503,16 @@ void launch_add_padded(float* out, const float* z, int64_t rows, int32_t d, int3
     if (blocks > 65536) blocks = 65536;
     hipLaunchKernelGGL(k_add_padded, dim3((unsigned)blocks), dim3(kBlock), 0, s, out, z, rows, d, ldz, bias,
                        accumulate, relu);
+}
+
+void launch_bias_act_bf16(void* out, const float* z, int64_t rows, int32_t d, int32_t ldz, const float* bias,
+                          int relu, hipStream_t s)
+{
+    if (rows <= 0 || d <= 0) return;
+    int64_t blocks = (rows * d + kBlock - 1) / kBlock;
+    if (blocks > 65536) blocks = 65536;
+    hipLaunchKernelGGL(k_bias_act_bf16, dim3((unsigned)blocks), dim3(kBlock), 0, s, (uint16_t*)out, z, rows, d,
+                       ldz, bias, relu);
 }
 
 void launch_pad_rows(float* dst, const float* src, int64_t rows, int32_t d, int32_t ld, hipStream_t s)

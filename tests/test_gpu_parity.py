@@ -246,8 +246,10 @@ def test_bf16_storage_matches_oracle(case, order):
             layer["Ws"] = to_bf16_grid(layer["Ws"])
     s = Session(model, dims, rowptr, colidx, k, mode, 3, X, w, y, m, dtype="bf16", layer_order=order)
     L = len(dims) - 1
-    # with bfloat16 storage only an output layer of whole 16-byte rows may transform first
-    want = [order == "auto" and l == L and dims[l] < dims[l - 1] and dims[l] % 8 == 0 for l in range(1, L + 1)]
+    # the cost rule of the fp32 path, for layers whose rows of H are whole 16-byte vectors; hidden
+    # layers only without a self term
+    want = [order == "auto" and dims[l] % 8 == 0 and (l == L or model == "gcn")
+            and 2 * dims[l] < dims[l - 1] * (3 if l >= 2 else 2) for l in range(1, L + 1)]
     assert [s.ctx.layer_is_transform_first(l) for l in range(1, L + 1)] == want
     loss = s.epoch()
     got = s.results()
