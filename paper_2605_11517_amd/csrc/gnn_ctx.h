@@ -77,7 +77,7 @@ struct gnn_ctx {
     char* staging = nullptr;
     char* scratch = nullptr;
     // layer order: 0 = aggregate, then transform (the paper's); 1 = transform first in layers
-    // that narrow (resident schedule, fp32)
+    // where that moves fewer rows (resident schedule)
     int32_t order_mode = 0;
     bool transform_first(int32_t layer) const
     {
