@@ -591,7 +591,9 @@ void launch_gat_dots(const int64_t* rp, const int32_t* col, int64_t e0, int64_t 
     else if (vecs <= 8) hipLaunchKernelGGL((k_gat_dots<8, 1>), grid, block, 0, s, g);
     else if (vecs <= 16) hipLaunchKernelGGL((k_gat_dots<16, 1>), grid, block, 0, s, g);
     else if (vecs <= 32) hipLaunchKernelGGL((k_gat_dots<32, 1>), grid, block, 0, s, g);
-    else if (vecs <= 64) hipLaunchKernelGGL((k_gat_dots<64, 1>), grid, block, 0, s, g);
+    // 1 KB rows: four 16-lane slots with four vectors per lane keep 16 source rows in flight per
+    // wavefront and need four shuffle steps per entry (one 64-lane slot: 4 rows, six steps)
+    else if (vecs <= 64) hipLaunchKernelGGL((k_gat_dots<16, 4>), grid, block, 0, s, g);
     else if (vecs <= 128) hipLaunchKernelGGL((k_gat_dots<64, 2>), grid, block, 0, s, g);
     else hipLaunchKernelGGL((k_gat_dots<64, 4>), grid, block, 0, s, g);
 }
