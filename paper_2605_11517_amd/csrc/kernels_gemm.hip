@@ -410,9 +410,17 @@ void launch_gemm(const GemmArgs& g, int splits, hipStream_t s)
                                dim3((unsigned)mt, (unsigned)nt, (unsigned)splits), dim3(kThreads), 0, s, ga); \
         }                                                                                       \
     } while (0)
+    // the last 128-wide column tile would be less than half used: 64-wide tiles waste less
+    // (172 columns: 192 computed instead of 256, 0.55 -> 0.42 ms on 780 k rows)
+    const bool tail64 = splits == 1 && (g.n + 63) / 64 * 64 < (g.n + 127) / 128 * 128;
+    // short K: the product is bound by its loads and stores, 64-row tiles keep more workgroups
+    // per CU in flight (+5 % at K = 128)
+    const bool small_k = splits == 1 && g.kseg[0] + g.kseg[1] <= 128;
 #define GNN_GEMM_TILE(VA, VB)                                     \
     do {                                                          \
-        if (big_m && big_n) GNN_GEMM(128, 128, VA, VB);           \
+        if (big_m && big_n && tail64) GNN_GEMM(128, 64, VA, VB);  \
+        else if (small_k && big_n) GNN_GEMM(64, 128, VA, VB);     \
+        else if (big_m && big_n) GNN_GEMM(128, 128, VA, VB);      \
         else if (big_m) GNN_GEMM(128, 64, VA, VB);                \
         else if (big_n) GNN_GEMM(64, 128, VA, VB);                \
         else GNN_GEMM(64, 64, VA, VB);                            \
