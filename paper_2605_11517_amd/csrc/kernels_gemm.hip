@@ -5,10 +5,12 @@
 //             grad W^l += Z_p^T dY_p                             reduction over the n_p rows
 //
 // One workgroup of 4 wavefronts (2 x 2) owns a BM x BN tile of C.  K is walked in steps of 16
-// through a double-buffered LDS stage; operands are stored in LDS k-major ([k][m] and [k][n])
-// so that the 32 lanes feeding one MFMA operand column read 32 consecutive floats.  Widths
-// that are not multiples of 4 floats (e.g. 47 classes) take a scalar-load variant of the same
-// kernel; tails in M, N and K are zero-filled in LDS, never in memory.
+// through a double-buffered LDS stage.  An operand whose k index is the contiguous one in
+// memory is kept [x][k] in LDS (chunks rotated per row, see kf_chunk) and an MFMA lane fetches
+// eight k of its row with two 16-byte reads; an operand whose m (or n) index is contiguous is
+// kept [k][x], so that the 32 lanes feeding one MFMA operand column read 32 consecutive floats.
+// Widths that are not multiples of 4 floats (e.g. 47 classes) take a scalar-load variant of the
+// same kernel; tails in M, N and K are zero-filled in LDS, never in memory.
 #include "gnn_internal.h"
 #include <cstdlib>
 

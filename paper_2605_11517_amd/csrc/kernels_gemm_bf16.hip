@@ -5,6 +5,12 @@
 //   backward  dZ_p   = dY_p (W^l)^T                           bf16 x bf16 -> bf16 / += fp32
 //             grad W^l += Z_p^T dY_p                          bf16 x bf16 -> fp32, split-K
 //
+// Two families.  The large products (at least 512 rows and 256 columns, K a multiple of 64, one
+// K segment) run on the 256 x 256 tile kernels further down (k_gemm_bf16_wide for k-contiguous
+// operands, k_gemm_bf16_tn_wide for the reduction over rows), which fill LDS with direct-to-LDS
+// loads.  Everything else (narrow output layers, ragged K, two-segment GraphSAGE products) runs
+// on the kernel described next.
+//
 // A workgroup of 4 wavefronts (2 x 2) owns a BM x BN tile of C and walks K in steps of 32.
 // An MFMA lane consumes eight consecutive k of its row as one 16-byte register group.
 // Operands that are k-contiguous in memory are kept [row][k] in LDS and fetched with one
