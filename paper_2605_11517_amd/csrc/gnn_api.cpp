@@ -446,20 +446,32 @@ static void xf_aggregate_fwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s
     float* segpart = (float*)(c->scratch + c->ws.segpart);
     const bool b16 = c->bf16();        // H and staging hold bfloat16 rows then; Z is fp32 either way
     const char* H = c->scratch + c->ws.h + r0 * dp * c->es();
-    {
-        Timed t(c, s, GNN_K_SPMM);
-        launch_spmm(c->D.rp + r0, c->D.lcol, c->D.ew, rscale, H, np, c->staging, Z, np, dp, b16 ? 1 : 0, 0, items,
-                    segpart, 1, SpmmScatter{}, s);
-    }
-    if (items.nlong > 0) {
-        Timed t(c, s, GNN_K_SPMM_REDUCE);
-        launch_spmm_reduce(rscale, Z, dp, 0, items, segpart, SpmmScatter{}, s);
-    }
     float* out = (float*)c->act[(size_t)layer - 1] + r0 * dout;
     const float* bias = c->has_bias ? (const float*)c->w[(size_t)3 * (layer - 1) + 2] : nullptr;
     const int relu = layer < c->L ? 1 : 0;
+    // Without a self term and without padding the aggregation finishes the layer itself: bias and
+    // activation are applied where a row's sum is stored, in the storage type of the output rows
+    const bool direct = c->model != GNN_SAGE_MEAN && dp == dout;
+    SpmmScatter fin;
+    if (direct) {
+        fin.bias = bias;
+        fin.relu = relu;
+    }
+    void* agg_out = direct ? (void*)(c->act[(size_t)layer - 1] + r0 * (int64_t)dout * c->act_es(layer)) : (void*)Z;
+    const int agg_out_bf16 = direct && b16 && layer < c->L ? 1 : 0;
+    {
+        Timed t(c, s, GNN_K_SPMM);
+        launch_spmm(c->D.rp + r0, c->D.lcol, c->D.ew, rscale, H, np, c->staging, agg_out, np, dp, b16 ? 1 : 0,
+                    agg_out_bf16, items, segpart, 1, fin, s);
+    }
+    if (items.nlong > 0) {
+        Timed t(c, s, GNN_K_SPMM_REDUCE);
+        launch_spmm_reduce(rscale, agg_out, dp, agg_out_bf16, items, segpart, fin, s);
+    }
     Timed t(c, s, GNN_K_GEMM_FWD);
-    if (c->model == GNN_SAGE_MEAN && b16) {
+    if (direct) {
+        // nothing left to do
+    } else if (c->model == GNN_SAGE_MEAN && b16) {
         GemmSegBf16 seg;
         seg.a = c->layer_input(layer, r0); seg.lda = din;
         seg.b = c->w[(size_t)3 * (layer - 1) + 1]; seg.ldb = dout; seg.k = din;

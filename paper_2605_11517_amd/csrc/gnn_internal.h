@@ -112,6 +112,9 @@ struct SpmmScatter {
     int64_t n_own = -1;
     int64_t base_row = 0;
     const int32_t* idx = nullptr;
+    // applied to what is stored (after the add, if any): + bias[column], then max(., 0)
+    const float* bias = nullptr;
+    int relu = 0;
 };
 // a_rows / b_rows hold fp32 (in_bf16 = 0) or bfloat16 rows; out is fp32 or bfloat16; the sums
 // and `partial` are always fp32.

@@ -113,6 +113,10 @@ struct SpmmArgs {
     // map_base + r when r < map_n_own, else to row map_idx[r - map_n_own]; map_n_own < 0 = off
     int64_t map_n_own, map_base;
     const int32_t* map_idx;
+    // applied to what is stored: + bias[column] (pointer already at this launch's first column),
+    // then max(., 0)
+    const float* bias;
+    int32_t relu;
     __device__ int64_t out_row(int32_t r) const
     {
         if (map_n_own < 0) return r;
@@ -258,7 +262,7 @@ __device__ inline void spmm_accumulate(const SpmmArgs& g, int64_t e_begin, int64
 // a bf16 input.
 template <typename TOut, int EPV, int G, int NV, bool VEC>
 __device__ inline void spmm_store(TOut* o, int32_t d, int lane, float sc, const float (&acc)[NV][EPV],
-                                  bool add = false)
+                                  bool add, const float* bias, bool relu)
 {
     if (lane >= G) return;
 #pragma unroll
@@ -279,6 +283,14 @@ __device__ inline void spmm_store(TOut* o, int32_t d, int lane, float sc, const 
 #pragma unroll
                     for (int i = 0; i < OPV; ++i) f[i] += old[i];
                 }
+                if (bias) {
+#pragma unroll
+                    for (int i = 0; i < OPV; ++i) f[i] += bias[c0 + h * OPV + i];
+                }
+                if (relu) {
+#pragma unroll
+                    for (int i = 0; i < OPV; ++i) f[i] = f[i] > 0.f ? f[i] : 0.f;
+                }
                 *dst = Elem<TOut>::pack(f);
             }
         } else {
@@ -287,6 +299,8 @@ __device__ inline void spmm_store(TOut* o, int32_t d, int lane, float sc, const 
                 if (c0 + i < d) {
                     float v2 = sc * acc[v][i];
                     if (add) v2 += Elem<TOut>::load(o + c0 + i);
+                    if (bias) v2 += bias[c0 + i];
+                    if (relu) v2 = v2 > 0.f ? v2 : 0.f;
                     Elem<TOut>::store(o + c0 + i, v2);
                 }
         }
@@ -311,7 +325,8 @@ __global__ __launch_bounds__(kBlock) void k_spmm_items(const SpmmArgs g)
             for (int i = 0; i < EPV; ++i) acc[v][i] = 0.f;
         const int64_t e0 = g.it.seg_begin[item];
         spmm_accumulate<TIn, G, NV, VEC>(g, e0, e0 + g.it.seg_len[item], lane, acc);
-        spmm_store<float, EPV, G, NV, VEC>(g.partial + item * (int64_t)g.ld, g.d, lane, 1.f, acc);
+        spmm_store<float, EPV, G, NV, VEC>(g.partial + item * (int64_t)g.ld, g.d, lane, 1.f, acc, false, nullptr,
+                                           false);
         return;
     }
     const int64_t ri = item - g.it.nsegs;
@@ -326,7 +341,8 @@ __global__ __launch_bounds__(kBlock) void k_spmm_items(const SpmmArgs g)
             for (int i = 0; i < EPV; ++i) acc[v][i] = 0.f;
         spmm_accumulate<TIn, G, NV, VEC>(g, e_begin, e_end, lane, acc);
         spmm_store<TOut, EPV, G, NV, VEC>(static_cast<TOut*>(g.out) + g.out_row(row) * (int64_t)g.ld, g.d,
-                                          lane, g.rowscale ? g.rowscale[row] : 1.f, acc, g.map_n_own >= 0);
+                                          lane, g.rowscale ? g.rowscale[row] : 1.f, acc, g.map_n_own >= 0,
+                                          g.bias, g.relu != 0);
     }
 }
 
@@ -447,6 +463,14 @@ __global__ __launch_bounds__(kBlock) void k_spmm_slots(const SpmmArgs g, int32_t
 #pragma unroll
                 for (int i = 0; i < OPV; ++i) f[i] += old[i];
             }
+            if (g.bias) {
+#pragma unroll
+                for (int i = 0; i < OPV; ++i) f[i] += g.bias[coff + h * OPV + i];
+            }
+            if (g.relu) {
+#pragma unroll
+                for (int i = 0; i < OPV; ++i) f[i] = f[i] > 0.f ? f[i] : 0.f;
+            }
             *reinterpret_cast<uint4*>(o + h * OPV) = Elem<TOut>::pack(f);
         }
     }
@@ -487,6 +511,8 @@ __global__ __launch_bounds__(kBlock) void k_spmm_long_reduce(const SpmmArgs g)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             if (add) o4[e] += Elem<TOut>::load(out + c + e);
+            if (g.bias) o4[e] += g.bias[c + e];
+            if (g.relu) o4[e] = o4[e] > 0.f ? o4[e] : 0.f;
             Elem<TOut>::store(out + c + e, o4[e]);
         }
     } else {
@@ -495,6 +521,8 @@ __global__ __launch_bounds__(kBlock) void k_spmm_long_reduce(const SpmmArgs g)
             for (int32_t t = 0; t < ns; ++t) s += g.partial[(first + t) * (int64_t)g.ld + c];
             s *= sc;
             if (add) s += Elem<TOut>::load(out + c);
+            if (g.bias) s += g.bias[c];
+            if (g.relu) s = s > 0.f ? s : 0.f;
             Elem<TOut>::store(out + c, s);
         }
     }
@@ -585,6 +613,7 @@ void spmm_typed(const int64_t* rp, const int32_t* col, const float* w, const flo
             g.a_rows = a_rows; g.n_a = n_a; g.b_rows = b_rows; g.out = out; g.d = d; g.ld = d;
             g.it = items; g.partial = partial;
             g.map_n_own = -1; g.map_base = 0; g.map_idx = nullptr;
+            g.bias = sc.bias; g.relu = sc.relu;
             const dim3 grid((unsigned)(blocks * ns));
             if (G == 16) hipLaunchKernelGGL((k_spmm_slots<TIn, TOut, 16>), grid, dim3(kBlock), 0, s, g, ns);
             else hipLaunchKernelGGL((k_spmm_slots<TIn, TOut, 32>), grid, dim3(kBlock), 0, s, g, ns);
@@ -611,6 +640,7 @@ void spmm_typed(const int64_t* rp, const int32_t* col, const float* w, const flo
         g.a_rows = a_rows; g.n_a = n_a; g.b_rows = b_rows; g.out = out; g.d = d; g.ld = d;
         g.it = items; g.partial = partial;
         g.map_n_own = sc.n_own; g.map_base = sc.base_row; g.map_idx = sc.idx;
+        g.bias = sc.bias; g.relu = sc.relu;
         const dim3 grid1((unsigned)blocks);
         if (G == 4) hipLaunchKernelGGL((k_spmm_slots<TIn, TOut, 4>), grid1, dim3(kBlock), 0, s, g, 1);
         else if (G == 8) hipLaunchKernelGGL((k_spmm_slots<TIn, TOut, 8>), grid1, dim3(kBlock), 0, s, g, 1);
@@ -632,6 +662,7 @@ void spmm_typed(const int64_t* rp, const int32_t* col, const float* w, const flo
         g.out = static_cast<TOut*>(out) + c0; g.d = dc; g.ld = d; g.it = items;
         g.partial = partial + c0;
         g.map_n_own = sc.n_own; g.map_base = sc.base_row; g.map_idx = sc.idx;
+        g.bias = sc.bias ? sc.bias + c0 : nullptr; g.relu = sc.relu;
         const int nv = (dc + EPV - 1) / EPV;  // 16-byte vectors per row in this block
 #define GNN_SPMM(G, NV, VEC) \
     hipLaunchKernelGGL((k_spmm_items<TIn, TOut, G, NV, VEC>), grid, block, 0, s, g)
@@ -662,6 +693,7 @@ void spmm_reduce_typed(const float* rowscale, void* out, int32_t d, const SpmmIt
     SpmmArgs g{};
     g.rowscale = rowscale; g.out = out; g.d = d; g.ld = d; g.it = items; g.partial = partial;
     g.map_n_own = sc.n_own; g.map_base = sc.base_row; g.map_idx = sc.idx;
+    g.bias = sc.bias; g.relu = sc.relu;
     const dim3 rgrid((unsigned)((items.nlong + wpb - 1) / wpb), (unsigned)((d + 255) / 256));
     if (d % 4 == 0) hipLaunchKernelGGL((k_spmm_long_reduce<TOut, true>), rgrid, dim3(kBlock), 0, s, g);
     else hipLaunchKernelGGL((k_spmm_long_reduce<TOut, false>), rgrid, dim3(kBlock), 0, s, g);
