@@ -1,8 +1,13 @@
-"""Parity at the bench's full size: the `mid` workload (2.4 M vertices, 131 M operator
-entries, 3-layer SAGE-mean, k = 16 label-propagation partitions) in exactly the launch
-configuration bench.py times, against one full fp64 oracle epoch on the host cores.
+"""Parity at the bench's full sizes.
 
-Needs about 60 GB of host memory and roughly two minutes (most of it the oracle)."""
+`mid` (2.4 M vertices, 131 M operator entries, 3-layer SAGE-mean, k = 16 switching-aware
+partitions) in exactly the launch configuration bench.py times, against one full fp64 oracle
+epoch on the host cores: about 60 GB of host memory and two minutes (most of it the oracle).
+
+`dense` (4 M vertices, bfloat16, GCN 512-1024-1024-64, k = 16) is too wide for a whole oracle
+epoch in reasonable time; there sampled rows and columns of every tensor are recomputed from
+their definitions, each from the path's own inputs to that step, which the oracle's
+aggregation routine and plain numpy can do one by one."""
 import os
 import sys
 import time
@@ -99,4 +104,104 @@ def test_mid_workload_full_size(capsys):
             worst["%s[%d]" % (key, l)] = rel_err(a, b)
     say("worst relative errors: " + ", ".join("%s=%.2g" % kv for kv in sorted(worst.items())))
     bad = {k_: v for k_, v in worst.items() if not v <= TOL}
+    assert not bad, bad
+
+
+BF16_TOL = 2e-2
+
+
+def test_dense_workload_sampled(capsys):
+    import psutil
+    if psutil.virtual_memory().available < 140 * 2 ** 30:
+        pytest.skip("needs ~100 GB of free host memory for the result tensors at full size")
+    from oracle import fullgraph as og
+    from paper_2605_11517_amd import Session
+    from synth import features, glorot_weights, labels_and_mask, make_config, to_bf16_grid
+
+    def say(msg):
+        with capsys.disabled():
+            print("[dense %.0fs] %s" % (time.time() - t0, msg), flush=True)
+
+    t0 = time.time()
+    cfg, rowptr, colidx = make_config("dense")
+    n, dims = cfg["n"], cfg["dims"]
+    X = to_bf16_grid(features(n, dims[0], cfg["seed"]))
+    y, m = labels_and_mask(n, dims[-1], cfg["train_frac"], cfg["seed"])
+    w = glorot_weights(dims, cfg["seed"], sage=False, bias_scale=0.05)
+    for layer in w:
+        layer["W"] = to_bf16_grid(layer["W"])
+    say("inputs ready: n=%d entries=%d" % (n, rowptr[-1]))
+    s = Session("gcn", dims, rowptr, colidx, cfg["k"], cfg["part"], cfg["seed"], X, w, y, m,
+                dtype="bf16", layer_order="auto")
+    assert [s.ctx.layer_is_transform_first(l) for l in (1, 2, 3)] == [False, True, True]
+    loss = s.epoch()
+    got = s.results()
+    del s
+    say("GPU epoch done, loss %.6f" % loss)
+    A = [X] + got["act"]                     # A[l]: activations the path itself produced
+    W = [np.asarray(l["W"], dtype=np.float64) for l in w]
+    b = [np.asarray(l["b"], dtype=np.float64) for l in w]
+
+    # the operator by its definition: deg(v) = row length, entry weight 1 / sqrt(deg(u) deg(v));
+    # the graph is symmetric, so the transposed operator has the same rows
+    deg = np.diff(rowptr).astype(np.float64)
+    inv = np.where(deg > 0, 1.0 / np.sqrt(np.maximum(deg, 1.0)), 0.0)
+    rng = np.random.default_rng(11)
+    V = np.unique(np.concatenate([rng.choice(n, 768, replace=False), np.argsort(deg)[-8:]]))
+
+    def agg_rows(rows_of, verts):
+        out = []
+        for v in verts:
+            cols = colidx[rowptr[v]:rowptr[v + 1]]
+            out.append((rows_of(cols) * inv[cols][:, None]).sum(axis=0) * inv[v])
+        return np.array(out)
+
+    worst = {}
+    # forward, layer by layer, each from the path's own previous activations
+    for l in (1, 2, 3):
+        z = agg_rows(lambda c, l=l: A[l - 1][c].astype(np.float64), V)
+        ref = z @ W[l - 1] + b[l - 1]
+        if l < 3:
+            ref = np.maximum(ref, 0.0)
+        worst["act[%d] rows" % (l - 1)] = rel_err(A[l][V], ref)
+    say("forward rows checked")
+
+    # loss and its gradient from the path's logits
+    lref, gref = og.loss(A[3], y, m)
+    assert abs(loss - lref) <= BF16_TOL * abs(lref)
+    worst["gact[2]"] = rel_err(got["gact"][2], gref)
+    dY3 = np.asarray(got["gact"][2], dtype=np.float64)
+
+    def at_times(Aleft, G):
+        """Aleft^T G in fp64, by row chunks."""
+        acc = np.zeros((Aleft.shape[1], G.shape[1]))
+        for r0 in range(0, n, 1 << 18):
+            acc += Aleft[r0:r0 + (1 << 18)].astype(np.float64).T @ G[r0:r0 + (1 << 18)]
+        return acc
+
+    # output layer (transform-first): grad H = S^T dY, grad W = A2^T grad H, grad A2 = grad H W^T
+    G3 = og.aggregate("gcn", rowptr, colidx, dY3, transpose=True)
+    worst["gW[2]"] = rel_err(got["gW"][2], at_times(A[2], G3))
+    worst["gb[2]"] = rel_err(got["gb"][2], dY3.sum(axis=0))
+    worst["gact[1] rows"] = rel_err(got["gact"][1][V], G3[V] @ W[2].T)
+    del G3
+    say("output layer checked")
+
+    # hidden layers on sampled columns (weight gradients) and sampled rows (input gradients)
+    J = np.sort(rng.choice(dims[2], 8, replace=False))
+    dY2J = np.where(A[2][:, J] > 0, got["gact"][1][:, J], 0.0).astype(np.float64)
+    G2J = og.aggregate("gcn", rowptr, colidx, dY2J, transpose=True)
+    worst["gW[1] cols"] = rel_err(got["gW"][1][:, J], at_times(A[1], G2J))
+    worst["gb[1] cols"] = rel_err(got["gb"][1][J], dY2J.sum(axis=0))
+    del G2J, dY2J
+    g2 = agg_rows(lambda c: np.where(A[2][c] > 0, got["gact"][1][c], 0.0).astype(np.float64), V)
+    worst["gact[0] rows"] = rel_err(got["gact"][0][V], g2 @ W[1].T)
+    J1 = np.sort(rng.choice(dims[1], 8, replace=False))
+    dY1J = np.where(A[1][:, J1] > 0, got["gact"][0][:, J1], 0.0).astype(np.float64)
+    # aggregate-first layer: grad W = (S X)^T dY = X^T (S^T dY)
+    G1J = og.aggregate("gcn", rowptr, colidx, dY1J, transpose=True)
+    worst["gW[0] cols"] = rel_err(got["gW"][0][:, J1], at_times(A[0], G1J))
+    worst["gb[0] cols"] = rel_err(got["gb"][0][J1], dY1J.sum(axis=0))
+    say("worst relative errors: " + ", ".join("%s=%.2g" % kv for kv in sorted(worst.items())))
+    bad = {k_: v for k_, v in worst.items() if not v <= BF16_TOL}
     assert not bad, bad
