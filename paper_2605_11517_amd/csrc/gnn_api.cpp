@@ -468,30 +468,34 @@ static void xf_aggregate_fwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s
         Timed t(c, s, GNN_K_SPMM_REDUCE);
         launch_spmm_reduce(rscale, agg_out, dp, agg_out_bf16, items, segpart, fin, s);
     }
-    Timed t(c, s, GNN_K_GEMM_FWD);
     if (direct) {
         // nothing left to do
-    } else if (c->model == GNN_SAGE_MEAN && b16) {
-        GemmSegBf16 seg;
-        seg.a = c->layer_input(layer, r0); seg.lda = din;
-        seg.b = c->w[(size_t)3 * (layer - 1) + 1]; seg.ldb = dout; seg.k = din;
-        GemmEpilogue ep;
-        ep.bias = bias;
-        launch_gemm_bf16_nn(&seg, 1, out, 0, dout, np, dout, ep, s);
-        launch_add_padded(out, Z, np, dout, dp, nullptr, 1, relu, s);
     } else if (c->model == GNN_SAGE_MEAN) {
-        const PaddedW ws = padded_weight(c, layer, 1);
-        GemmSeg seg;
-        seg.a = (const float*)c->layer_input(layer, r0); seg.lda = din;
-        seg.b = ws.p; seg.ldb = ws.ld; seg.k = din;
-        GemmEpilogue ep;
-        ep.bias = bias;
-        launch_gemm_nn(&seg, 1, out, dout, np, dout, ep, s);
+        {
+            Timed t(c, s, GNN_K_GEMM_FWD);
+            GemmEpilogue ep;
+            ep.bias = bias;
+            if (b16) {
+                GemmSegBf16 seg;
+                seg.a = c->layer_input(layer, r0); seg.lda = din;
+                seg.b = c->w[(size_t)3 * (layer - 1) + 1]; seg.ldb = dout; seg.k = din;
+                launch_gemm_bf16_nn(&seg, 1, out, 0, dout, np, dout, ep, s);
+            } else {
+                const PaddedW ws = padded_weight(c, layer, 1);
+                GemmSeg seg;
+                seg.a = (const float*)c->layer_input(layer, r0); seg.lda = din;
+                seg.b = ws.p; seg.ldb = ws.ld; seg.k = din;
+                launch_gemm_nn(&seg, 1, out, dout, np, dout, ep, s);
+            }
+        }
+        Timed t(c, s, GNN_K_OTHER);
         launch_add_padded(out, Z, np, dout, dp, nullptr, 1, relu, s);
     } else if (b16 && layer < c->L) {
         // hidden layer with bfloat16 storage: the output rows are rounded once, here
+        Timed t(c, s, GNN_K_OTHER);
         launch_bias_act_bf16(c->act[(size_t)layer - 1] + r0 * (int64_t)dout * 2, Z, np, dout, dp, bias, relu, s);
     } else {
+        Timed t(c, s, GNN_K_OTHER);
         launch_add_padded(out, Z, np, dout, dp, bias, 0, relu, s);
     }
     if (c->dropout_p > 0.f && layer < c->L) {

@@ -339,40 +339,54 @@ __global__ __launch_bounds__(kThreads) void k_gemm(const GemmArgs g)
         }
 }
 
-// c[i] += sum_s partial[s * stride + i], s ascending; four consecutive elements per thread,
-// eight splits in flight.
+// c[i] += sum_s partial[s * stride + i].  A block covers 64 groups of four consecutive
+// elements; its four wavefronts each add a quarter of the splits (ascending, eight loads in
+// flight) and the four sums are combined through LDS in wavefront order, so the result does
+// not depend on timing.  (One thread per group over all splits left most of the chip idle: a
+// 256 x 256 gradient is only 64 such blocks of 256 threads.)
 __global__ __launch_bounds__(256) void k_reduce_partials(const float* __restrict__ partial,
                                                          int32_t splits, int64_t stride,
                                                          float* __restrict__ c, int64_t ldc,
                                                          int32_t m, int32_t n)
 {
     constexpr int U = 8;
+    __shared__ float4 sm[4][64];
     const int64_t total = (int64_t)m * n;
-    const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
-    if (i >= total) return;
-    const bool full = (i + 3 < total) && (stride % 4 == 0);
+    const int grp = threadIdx.x & 63, q = threadIdx.x >> 6;
+    const int64_t i = ((int64_t)blockIdx.x * 64 + grp) * 4;
+    const int32_t per = (splits + 3) / 4;
+    const int32_t zb = q * per, ze = zb + per < splits ? zb + per : splits;
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
-    if (full) {
-        for (int32_t z0 = 0; z0 < splits; z0 += U) {
-            float4 x[U];
+    if (i < total) {
+        const bool full = (i + 3 < total) && (stride % 4 == 0);
+        if (full) {
+            for (int32_t z0 = zb; z0 < ze; z0 += U) {
+                float4 x[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u)
-                x[u] = z0 + u < splits
-                           ? *reinterpret_cast<const float4*>(partial + (int64_t)(z0 + u) * stride + i)
-                           : make_float4(0.f, 0.f, 0.f, 0.f);
+                for (int u = 0; u < U; ++u)
+                    x[u] = z0 + u < ze
+                               ? *reinterpret_cast<const float4*>(partial + (int64_t)(z0 + u) * stride + i)
+                               : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-            for (int u = 0; u < U; ++u) { acc[0] += x[u].x; acc[1] += x[u].y; acc[2] += x[u].z; acc[3] += x[u].w; }
+                for (int u = 0; u < U; ++u) { acc[0] += x[u].x; acc[1] += x[u].y; acc[2] += x[u].z; acc[3] += x[u].w; }
+            }
+        } else {
+            for (int32_t z = zb; z < ze; ++z)
+                for (int e = 0; e < 4; ++e)
+                    if (i + e < total) acc[e] += partial[(int64_t)z * stride + i + e];
         }
-    } else {
-        for (int32_t z = 0; z < splits; ++z)
-            for (int e = 0; e < 4; ++e)
-                if (i + e < total) acc[e] += partial[(int64_t)z * stride + i + e];
     }
+    sm[q][grp] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+    __syncthreads();
+    if (q != 0 || i >= total) return;
+    float4 t = sm[0][grp];
+    for (int w = 1; w < 4; ++w) { t.x += sm[w][grp].x; t.y += sm[w][grp].y; t.z += sm[w][grp].z; t.w += sm[w][grp].w; }
+    const float out[4] = {t.x, t.y, t.z, t.w};
     for (int e = 0; e < 4; ++e) {
-        const int64_t j = i + e;
-        if (j >= total) break;
-        const int64_t r = j / n, cc = j - r * n;
-        c[r * ldc + cc] += acc[e];
+        const int64_t j2 = i + e;
+        if (j2 >= total) break;
+        const int64_t r = j2 / n, cc = j2 - r * n;
+        c[r * ldc + cc] += out[e];
     }
 }
 
@@ -516,7 +530,7 @@ void launch_gemm_tn(const float* a, int64_t lda, const float* b, int64_t ldb, fl
 void launch_reduce_partials(const float* partial, int splits, int64_t stride, float* c, int64_t ldc,
                             int32_t m, int32_t n, hipStream_t s)
 {
-    int64_t blocks = ((int64_t)m * n + 1023) / 1024;
+    int64_t blocks = ((int64_t)m * n + 255) / 256;
     hipLaunchKernelGGL(k_reduce_partials, dim3((unsigned)blocks), dim3(256), 0, s, partial, splits,
                        stride, c, ldc, m, n);
 }
