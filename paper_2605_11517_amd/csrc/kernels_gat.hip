@@ -413,15 +413,27 @@ __device__ inline void dot_entries(const GatDotArgs& g, int32_t row, int64_t eb,
                           : make_float4(0.f, 0.f, 0.f, 0.f);
         if (cv[v] < 0) cv[v] = 0;
     }
+    if (eb >= ee) return;
+    // the column indices of a batch are fetched one batch ahead, so that the row loads of a batch
+    // do not wait for an index load first
+    int32_t cnext[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int64_t ee_u = eb + u * S + slot;
+        cnext[u] = g.col[ee_u < ee ? ee_u : ee - 1];
+    }
     for (int64_t e = eb; e < ee; e += S * U) {
         float acc[U];
         const float* src[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int64_t ee_u = e + u * S + slot;
-            const int64_t ec = ee_u < ee ? ee_u : ee - 1;
-            const int32_t c = g.col[ec];
+            const int32_t c = cnext[u];
             src[u] = c < g.n_own ? g.a_rows + (int64_t)c * g.ld : g.b_rows + ((int64_t)c - g.n_own) * g.ld;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t ee_u = e + S * U + u * S + slot;
+            cnext[u] = g.col[ee_u < ee ? ee_u : ee - 1];
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
