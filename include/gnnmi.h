@@ -345,6 +345,8 @@ typedef struct {
     int64_t act_loads, act_hits;
     int64_t grad_loads, grad_hits, grad_writebacks;
     int64_t h2d_bytes, d2h_bytes;
+    int64_t direct_gathers; /* (partition, source block) pairs whose boundary rows a kernel read */
+    int64_t direct_bytes;   /* straight from the pinned host array, and their bytes (in h2d_bytes) */
 } gnn_stream_stats;
 gnn_status gnn_get_stream_stats(const gnn_ctx *ctx, gnn_stream_stats *out);
 

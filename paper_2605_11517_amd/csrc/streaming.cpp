@@ -57,6 +57,7 @@ struct BlockCache {
     std::vector<int32_t> slot_of;   // partition -> slot or -1
     std::vector<uint8_t> touched;   // write-back cache: block exists (on host or in a slot)
     char* host = nullptr;           // backing array
+    const char* host_dev = nullptr; // the same memory as kernels see it (null: not mapped for the device)
     bool writeback = false;
     bool identity = false;          // a whole array: block p lives in slot p and is never evicted
     int32_t cur_t = 0;              // step (position in the partition order) whose accesses are being issued
@@ -90,6 +91,7 @@ struct StreamEngine {
     std::vector<int32_t> next_dep;
     int32_t k = 0;
     int64_t h2d_bytes = 0, d2h_bytes = 0;   // of the running epoch
+    int64_t direct_gathers = 0, direct_bytes = 0;   // boundary rows read straight from host memory
     int64_t loads[2] = {0, 0}, hits[2] = {0, 0}, writebacks = 0;
     char* io = nullptr;             // 6 transfer buffers
     int64_t io_bytes = 0;           // bytes of one buffer
@@ -169,6 +171,17 @@ gnn_status new_slot(gnn_ctx* c, StreamEngine& E, Slot& out)
 }
 
 // (Re)cuts a cache over `pool_bytes` at `pool` into slots of `slot_bytes`; contents are dropped.
+// Boundary rows of blocks that are not in the cache are gathered by the kernel straight from
+// the pinned host array (GNNMI_STREAM_DIRECT=0: every miss loads the whole block instead).
+bool direct_gather_enabled()
+{
+    static const bool on = [] {
+        const char* e = std::getenv("GNNMI_STREAM_DIRECT");
+        return !(e && e[0] == '0');
+    }();
+    return on;
+}
+
 gnn_status configure(gnn_ctx* c, StreamEngine& E, BlockCache& bc, char* pool, int64_t pool_bytes,
                      int64_t slot_bytes, int64_t row_bytes, char* host, bool writeback, bool identity)
 {
@@ -185,6 +198,15 @@ gnn_status configure(gnn_ctx* c, StreamEngine& E, BlockCache& bc, char* pool, in
     bc.slot_bytes = slot_bytes;
     bc.row_bytes = row_bytes;
     bc.host = host;
+    bc.host_dev = nullptr;
+    if (host && !writeback && !identity && direct_gather_enabled()) {
+        // pinned host memory that is mapped for the device can be read by kernels directly
+        hipPointerAttribute_t at;
+        if (hipPointerGetAttributes(&at, host) == hipSuccess && at.type == hipMemoryTypeHost && at.devicePointer)
+            bc.host_dev = (const char*)at.devicePointer;
+        else
+            (void)hipGetLastError();
+    }
     bc.writeback = writeback;
     bc.identity = identity;
     while ((int64_t)bc.slots.size() > n) {
@@ -341,6 +363,13 @@ gnn_status mark_used(gnn_ctx* c, BlockCache& bc, int32_t s, hipStream_t compute,
     return GNN_OK;
 }
 
+inline bool has_empty_slot(const BlockCache& bc)
+{
+    for (const Slot& sl : bc.slots)
+        if (sl.part < 0) return true;
+    return false;
+}
+
 // Gather of the boundary rows of the partition of step t from the cached blocks of layer l-1,
 // one source partition at a time.  Leaves the own block pinned and returns its slot.
 gnn_status gather_from_cache(gnn_ctx* c, StreamEngine& E, BlockCache& bc, int32_t layer, int32_t t,
@@ -361,6 +390,18 @@ gnn_status gather_from_cache(gnn_ctx* c, StreamEngine& E, BlockCache& bc, int32_
         const int64_t len = run[q + 1] - run[q];
         if (len <= 0) continue;
         int32_t sq;
+        if (bc.host_dev && bc.slot_of[(size_t)q] < 0 && !has_empty_slot(bc)) {
+            // Not cached, and caching it would evict a block that every later partition also
+            // needs: read just the rows over the link.  (A partition depends on nearly every
+            // other one, so a cache smaller than the array cycles whole blocks for a fraction of
+            // their rows; the kernel reads pinned host rows at the full rate of the link.)
+            launch_gather_rows(bc.host_dev + M.off[(size_t)q] * row_bytes, c->D.bnd_local + b0 + run[q],
+                               c->staging + run[q] * row_bytes, len, row_bytes, s);
+            ++E.direct_gathers;
+            E.direct_bytes += len * row_bytes;
+            E.h2d_bytes += len * row_bytes;
+            continue;
+        }
         if ((st = acquire(c, E, bc, q, s, true, &sq)) != GNN_OK) return st;
         if (flat) continue;
         launch_gather_rows(bc.ptr(sq), c->D.bnd_local + b0 + run[q], c->staging + run[q] * row_bytes,
@@ -390,6 +431,7 @@ gnn_status prefetch_for(gnn_ctx* c, StreamEngine& E, BlockCache& bc, int32_t t, 
     for (int32_t q = 0; q < k && budget > 0; ++q) {
         if (run[q + 1] - run[q] <= 0) continue;
         if (bc.slot_of[(size_t)q] < 0) {
+            if (bc.host_dev && !has_empty_slot(bc)) break;   // its rows will be read from the host
             if ((st = acquire(c, E, bc, q, s, false, &slot)) != GNN_OK) return st;
             if (slot < 0) break;
         }
@@ -619,6 +661,7 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
     E.has_in_released[0] = E.has_in_released[1] = false;
     E.h2d_bytes = E.d2h_bytes = 0;
     E.loads[0] = E.loads[1] = E.hits[0] = E.hits[1] = E.writebacks = 0;
+    E.direct_gathers = E.direct_bytes = 0;
 
     zero_weight_grads(c, s);
 
@@ -967,6 +1010,8 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
     c->stream_stats.grad_writebacks = E.writebacks;
     c->stream_stats.h2d_bytes = E.h2d_bytes;
     c->stream_stats.d2h_bytes = E.d2h_bytes;
+    c->stream_stats.direct_gathers = E.direct_gathers;
+    c->stream_stats.direct_bytes = E.direct_bytes;
     return check_launch(c, "gnn_epoch (streaming)");
 }
 
