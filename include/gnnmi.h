@@ -193,13 +193,18 @@ gnn_status gnn_workspace_bytes(const gnn_ctx *ctx, int64_t *staging, int64_t *sc
  * Streaming schedule (hbm_budget_bytes > 0; the one-GPU analogue of the paper's partition-wise
  * cache with copy/compute overlap): feat, act[] and grad_act[] are PINNED HOST buffers of the
  * same shapes and order; everything else stays device memory.  The library then allocates
- * hbm_budget_bytes of device memory as a cache of partition blocks (layer l-1 activations,
- * least-recently-used eviction; gradient blocks of layer l-1 as a write-back cache) plus six
+ * hbm_budget_bytes of device memory as a cache of whole per-layer arrays while they fit and of
+ * single partition blocks otherwise (layer l-1 activations, the block whose next use lies
+ * furthest ahead is evicted; gradient blocks of layer l-1 as a write-back cache) plus six
  * transfer buffers of max n_p x max d_l x 4 bytes and two side streams, all freed by
  * gnn_destroy or the next gnn_build_partitions.  Only gnn_epoch runs in this mode (the
  * per-partition entry points return GNN_EUNSUPPORTED), at most 4096 partitions, and the budget
  * must hold two activation blocks and two gradient blocks of the widest layer (GNN_ENOMEM
- * otherwise).  Results are bit-identical to the resident schedule.
+ * otherwise).  When the host buffers are mapped for the device (hipHostMalloc, or torch's
+ * pin_memory: hipPointerGetAttributes reports a device pointer), boundary rows of blocks that
+ * are not cached are read by the gather kernel directly from them; with host memory that is
+ * not mapped every miss loads its whole block.  Results are bit-identical to the resident
+ * schedule either way.
  *
  * Errors: GNN_ESTATE before gnn_build_partitions, GNN_EINVAL on a null entry,
  * GNN_EHIP / GNN_ENOMEM if the upload or an allocation fails. */
