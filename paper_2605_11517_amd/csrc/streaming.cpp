@@ -592,8 +592,11 @@ gnn_status stream_engine_create(gnn_ctx* c)
         return c->fail(e == hipErrorOutOfMemory ? GNN_ENOMEM : GNN_EHIP, msg);
     };
     hipError_t e;
-    if ((e = hipStreamCreate(&E->h2d)) != hipSuccess) return fail_hip(e, "hipStreamCreate");
-    if ((e = hipStreamCreate(&E->d2h)) != hipSuccess) return fail_hip(e, "hipStreamCreate");
+    // Non-blocking: a caller's compute stream may be the null stream, which would otherwise
+    // order itself against every copy on these two (each kernel waiting for the copy before it
+    // and the other way round); all real dependencies are expressed with events.
+    if ((e = hipStreamCreateWithFlags(&E->h2d, hipStreamNonBlocking)) != hipSuccess) return fail_hip(e, "hipStreamCreate");
+    if ((e = hipStreamCreateWithFlags(&E->d2h, hipStreamNonBlocking)) != hipSuccess) return fail_hip(e, "hipStreamCreate");
     if ((e = hipMalloc((void**)&E->pool, (size_t)E->pool_bytes)) != hipSuccess) return fail_hip(e, "hipMalloc(block cache)");
     if ((e = hipMalloc((void**)&E->io, (size_t)(6 * E->io_bytes))) != hipSuccess) return fail_hip(e, "hipMalloc(transfer buffers)");
     E->free_list.assign(1, {0, E->pool_bytes});
