@@ -4,6 +4,10 @@
 partitions) in exactly the launch configuration bench.py times, against one full fp64 oracle
 epoch on the host cores: about 60 GB of host memory and two minutes (most of it the oracle).
 
+The streaming schedule on `mid` with pools far smaller than the working set must reproduce the
+resident schedule bit for bit: at this size kernels run for milliseconds beside the copies, so
+a missing dependency between the three streams would show.
+
 `dense` (4 M vertices, bfloat16, GCN 512-1024-1024-64, k = 16) is too wide for a whole oracle
 epoch in reasonable time; there sampled rows and columns of every tensor are recomputed from
 their definitions, each from the path's own inputs to that step, which the oracle's
@@ -105,6 +109,46 @@ def test_mid_workload_full_size(capsys):
     say("worst relative errors: " + ", ".join("%s=%.2g" % kv for kv in sorted(worst.items())))
     bad = {k_: v for k_, v in worst.items() if not v <= TOL}
     assert not bad, bad
+
+
+def test_mid_streaming_matches_resident_bit_for_bit(capsys):
+    import psutil
+    if psutil.virtual_memory().available < 60 * 2 ** 30:
+        pytest.skip("needs ~40 GB of free host memory")
+    from paper_2605_11517_amd import Session
+    from synth import features, glorot_weights, labels_and_mask, make_config
+
+    def say(msg):
+        with capsys.disabled():
+            print("[stream %.0fs] %s" % (time.time() - t0, msg), flush=True)
+
+    t0 = time.time()
+    cfg, rowptr, colidx = make_config("mid")
+    n, dims = cfg["n"], cfg["dims"]
+    X = features(n, dims[0], cfg["seed"])
+    y, m = labels_and_mask(n, dims[-1], cfg["train_frac"], cfg["seed"])
+    w = glorot_weights(dims, cfg["seed"], sage=True, bias_scale=0.05)
+    s = Session("sage", dims, rowptr, colidx, cfg["k"], cfg["part"], cfg["seed"], X, w, y, m)
+    loss = s.epoch()
+    ref = s.results()
+    del s
+    say("resident epoch done, loss %.6f" % loss)
+    for gib, epochs in ((4, 2), (1.5, 1)):
+        s = Session("sage", dims, rowptr, colidx, cfg["k"], cfg["part"], cfg["seed"], X, w, y, m,
+                    hbm_budget_bytes=int(gib * 2 ** 30))
+        for rep in range(epochs):
+            assert s.epoch() == loss
+            got = s.results()
+            for key in ("act", "gact", "gW", "gWs", "gb"):
+                for l, (a, b) in enumerate(zip(got[key], ref[key])):
+                    assert np.array_equal(a, b), (gib, rep, key, l)
+            st = s.ctx.get_stream_stats()
+            say("pool %g GiB, epoch %d bit-identical; %d block loads, %d direct row gathers, %.1f GB in, %.1f GB out"
+                % (gib, rep, st["act_loads"] + st["grad_loads"], st["direct_gathers"], st["h2d_bytes"] / 1e9,
+                   st["d2h_bytes"] / 1e9))
+        # pools this small cannot hold the gather source: blocks are loaded and rows are read directly
+        assert st["act_loads"] > cfg["k"] and st["direct_gathers"] > 0
+        del s
 
 
 BF16_TOL = 2e-2
