@@ -115,3 +115,84 @@ def ring_of_blocks(k, per, seed):
     pairs = np.unique(np.array(dst, dtype=np.int64) * n + np.array(src, dtype=np.int64))
     rowptr, colidx = csr_from_edges(n, pairs % n, pairs // n)
     return rowptr, colidx, part, label
+
+
+def gat_sampled_errors(rowptr, colidx, dims, weights, X, act, gact, gb, V, say=None):
+    """Graph-attention layers checked on the sampled vertices ``V`` of a symmetric graph whose
+    CSR holds no self-loops: rows ``V`` of every layer's output, every bias gradient, and rows
+    ``V`` of every hidden input gradient, each recomputed in fp64 from the layer's definition
+    (one head, LeakyReLU slope 0.2, one self-loop per vertex) and from the given tensors of the
+    step before (``act``: A^1..A^L, ``gact``: dLoss/dA^1..dLoss/dA^L).  Returns the relative
+    errors by name.
+
+    The softmax gradient of an edge u -> v needs sum_u' alpha(u' -> v) dY[v] . H[u'], which is
+    dY[v] . Z[v]; Z = A^l - b wherever dY is not zero (dY vanishes where the ReLU is off)."""
+    n = len(rowptr) - 1
+    L = len(dims) - 1
+    deg = np.diff(rowptr)
+    dst = np.concatenate([np.repeat(np.arange(n, dtype=np.int64), deg), np.arange(n, dtype=np.int64)])
+    src = np.concatenate([np.asarray(colidx, dtype=np.int64), np.arange(n, dtype=np.int64)])
+    assert not np.any(dst[:rowptr[-1]] == src[:rowptr[-1]])
+    assert np.array_equal(np.bincount(colidx, minlength=n), deg)        # mirrored edges
+    A = [X] + list(act)
+
+    def leaky(x):
+        return np.where(x > 0, x, 0.2 * x)
+
+    def around(v):
+        """Sources of v (= targets of v: the graph is symmetric), v itself included."""
+        return np.concatenate([np.asarray(colidx[rowptr[v]:rowptr[v + 1]], dtype=np.int64), [v]])
+
+    worst = {}
+    for l in range(L, 0, -1):
+        W = np.asarray(weights[l - 1]["W"], dtype=np.float64)
+        a_s = np.asarray(weights[l - 1]["a_src"], dtype=np.float64)
+        a_d = np.asarray(weights[l - 1]["a_dst"], dtype=np.float64)
+        b = np.asarray(weights[l - 1]["b"], dtype=np.float64)
+        H = np.empty((n, dims[l]))
+        for r0 in range(0, n, 1 << 18):
+            H[r0:r0 + (1 << 18)] = np.asarray(A[l - 1][r0:r0 + (1 << 18)], dtype=np.float64) @ W
+        s_src, s_dst = H @ a_s, H @ a_d
+
+        # forward rows by the definition
+        ref = []
+        for v in V:
+            u = around(v)
+            e = leaky(s_src[u] + s_dst[v])
+            ex = np.exp(e - e.max())
+            z = (ex / ex.sum()) @ H[u] + b
+            ref.append(np.maximum(z, 0.0) if l < L else z)
+        worst["act[%d] rows" % (l - 1)] = rel_err(np.asarray(A[l])[V], np.array(ref))
+
+        # per-vertex softmax statistics over all edges, then the input gradient of sampled rows
+        e = leaky(s_src[src] + s_dst[dst])
+        mx = np.full(n, -np.inf)
+        np.maximum.at(mx, dst, e)
+        den = np.zeros(n)
+        np.add.at(den, dst, np.exp(e - mx[dst]))
+        del e
+        dY = np.asarray(gact[l - 1], dtype=np.float64)
+        if l < L:
+            dY = np.where(np.asarray(A[l]) > 0, dY, 0.0)
+        c = np.einsum("ij,ij->i", dY, np.asarray(A[l], dtype=np.float64) - b)
+        worst["gb[%d]" % (l - 1)] = rel_err(gb[l - 1], dY.sum(axis=0))
+        if l == 1:
+            break                                   # the gradient of the input features is not kept
+        ref = []
+        for u in V:
+            t = around(u)
+            # edges u -> t
+            x = s_src[u] + s_dst[t]
+            alpha = np.exp(leaky(x) - mx[t]) / den[t]
+            dx = alpha * (dY[t] @ H[u] - c[t]) * np.where(x > 0, 1.0, 0.2)
+            dH = alpha @ dY[t] + dx.sum() * a_s
+            # edges t -> u
+            x = s_src[t] + s_dst[u]
+            alpha = np.exp(leaky(x) - mx[u]) / den[u]
+            dx = alpha * (H[t] @ dY[u] - c[u]) * np.where(x > 0, 1.0, 0.2)
+            dH = dH + dx.sum() * a_d
+            ref.append(dH @ W.T)
+        worst["gact[%d] rows" % (l - 2)] = rel_err(np.asarray(gact[l - 2])[V], np.array(ref))
+        if say:
+            say("layer %d checked" % l)
+    return worst

@@ -11,7 +11,11 @@ a missing dependency between the three streams would show.
 `dense` (4 M vertices, bfloat16, GCN 512-1024-1024-64, k = 16) is too wide for a whole oracle
 epoch in reasonable time; there sampled rows and columns of every tensor are recomputed from
 their definitions, each from the path's own inputs to that step, which the oracle's
-aggregation routine and plain numpy can do one by one."""
+aggregation routine and plain numpy can do one by one.
+
+`mid_gat` (graph attention on the `mid` graph): sampled vertices, eight hubs among them, of
+every layer's output and input gradient, by a helper that a CPU test pins to the oracle's
+whole-graph epoch."""
 import os
 import sys
 import time
@@ -19,7 +23,7 @@ import time
 import numpy as np
 import pytest
 
-from helpers import aligned_backward, rel_err
+from helpers import aligned_backward, gat_sampled_errors, rel_err
 
 pytestmark = pytest.mark.gpu
 TOL = 1e-4
@@ -248,4 +252,48 @@ def test_dense_workload_sampled(capsys):
     worst["gb[0] cols"] = rel_err(got["gb"][0][J1], dY1J.sum(axis=0))
     say("worst relative errors: " + ", ".join("%s=%.2g" % kv for kv in sorted(worst.items())))
     bad = {k_: v for k_, v in worst.items() if not v <= BF16_TOL}
+    assert not bad, bad
+
+
+def test_mid_gat_workload_sampled(capsys):
+    """Graph attention at the bench's `mid_gat` size.  A whole oracle epoch would need the
+    edge-by-feature products of 134 M edges in memory; instead every layer's outputs and input
+    gradients are recomputed for sampled vertices (eight hubs among them) from the layer's
+    definition, one vertex at a time, from the path's own inputs to that step.  The softmax
+    gradient of an edge u -> v needs sum_u' alpha(u' -> v) dY[v] . H[u'], which equals
+    dY[v] . Z[v]: a per-vertex dot product."""
+    import psutil
+    if psutil.virtual_memory().available < 60 * 2 ** 30:
+        pytest.skip("needs ~40 GB of free host memory")
+    from oracle import fullgraph as og
+    from paper_2605_11517_amd import Session
+    from synth import attention_vectors, features, glorot_weights, labels_and_mask, make_config
+
+    def say(msg):
+        with capsys.disabled():
+            print("[gat %.0fs] %s" % (time.time() - t0, msg), flush=True)
+
+    t0 = time.time()
+    cfg, rowptr, colidx = make_config("mid_gat")
+    n, dims = cfg["n"], cfg["dims"]
+    L = len(dims) - 1
+    assert cfg["symmetric"] and not cfg["self_loops"]
+    X = features(n, dims[0], cfg["seed"])
+    y, m = labels_and_mask(n, dims[-1], cfg["train_frac"], cfg["seed"])
+    w = attention_vectors(glorot_weights(dims, cfg["seed"], sage=False, bias_scale=0.05), cfg["seed"])
+    say("inputs ready: n=%d entries=%d" % (n, rowptr[-1]))
+    s = Session("gat", dims, rowptr, colidx, cfg["k"], cfg["part"], cfg["seed"], X, w, y, m)
+    loss = s.epoch()
+    got = s.results()
+    del s
+    say("GPU epoch done, loss %.6f" % loss)
+    deg = np.diff(rowptr)
+    rng = np.random.default_rng(5)
+    V = np.unique(np.concatenate([rng.choice(n, 504, replace=False), np.argsort(deg)[-8:]]))
+    lref, gref = og.loss(got["act"][L - 1], y, m)
+    assert abs(loss - lref) <= TOL * abs(lref)
+    worst = {"gact[%d]" % (L - 1): rel_err(got["gact"][L - 1], gref)}
+    worst.update(gat_sampled_errors(rowptr, colidx, dims, w, X, got["act"], got["gact"], got["gb"], V, say))
+    say("worst relative errors: " + ", ".join("%s=%.2g" % kv for kv in sorted(worst.items())))
+    bad = {k_: v for k_, v in worst.items() if not v <= TOL}
     assert not bad, bad

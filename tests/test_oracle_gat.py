@@ -139,3 +139,25 @@ def test_attention_is_invariant_to_a_shift_of_the_destination_score_sign_region(
     _, cache3 = gat.layer_forward(dst, src, n, H_in, W, -a_src, a_dst, None, relu=False)
     want3 = np.exp(-0.2 * a_src) / np.exp(-0.2 * a_src).sum()
     assert np.abs(cache3["alpha"][:6] - want3).max() < 1e-14
+
+
+def test_sampled_row_check_agrees_with_the_whole_graph_epoch():
+    """The per-vertex recomputation that the full-size GPU test uses (helpers.gat_sampled_errors)
+    reproduces the oracle's whole-graph epoch on every vertex, and reports a planted mistake in
+    an input gradient or an output row."""
+    from helpers import gat_sampled_errors
+    dims = (9, 12, 10, 5)
+    rowptr, colidx, X, y, m, w = make(70, dims, seed=8)
+    ref = gat.epoch(rowptr, colidx, dims, X, w, y, m)
+    V = np.arange(70)
+    errs = gat_sampled_errors(rowptr, colidx, dims, w, X, ref["act"], ref["gact"], ref["gb"], V)
+    assert set(errs) == {"act[0] rows", "act[1] rows", "act[2] rows", "gb[0]", "gb[1]", "gb[2]",
+                         "gact[0] rows", "gact[1] rows"}
+    assert max(errs.values()) < 1e-12, errs
+    # a dropped destination-score term in one input gradient, and a shifted output row
+    bad_g = [g.copy() for g in ref["gact"]]
+    bad_g[0][17] *= 1.01
+    assert gat_sampled_errors(rowptr, colidx, dims, w, X, ref["act"], bad_g, ref["gb"], V)["gact[0] rows"] > 1e-4
+    bad_a = [a.copy() for a in ref["act"]]
+    bad_a[1][3, 2] += 0.01
+    assert gat_sampled_errors(rowptr, colidx, dims, w, X, bad_a, ref["gact"], ref["gb"], V)["act[1] rows"] > 1e-4
