@@ -15,7 +15,10 @@ aggregation routine and plain numpy can do one by one.
 
 `mid_gat` (graph attention on the `mid` graph): sampled vertices, eight hubs among them, of
 every layer's output and input gradient, by a helper that a CPU test pins to the oracle's
-whole-graph epoch."""
+whole-graph epoch.
+
+`large` (50 M vertices, 868 M entries, k = 64): the same kind of sampled check with the tensors
+left on the device; opt-in (GNNMI_TEST_LARGE=1) because it runs for seven minutes."""
 import os
 import sys
 import time
@@ -294,6 +297,152 @@ def test_mid_gat_workload_sampled(capsys):
     assert abs(loss - lref) <= TOL * abs(lref)
     worst = {"gact[%d]" % (L - 1): rel_err(got["gact"][L - 1], gref)}
     worst.update(gat_sampled_errors(rowptr, colidx, dims, w, X, got["act"], got["gact"], got["gb"], V, say))
+    say("worst relative errors: " + ", ".join("%s=%.2g" % kv for kv in sorted(worst.items())))
+    bad = {k_: v for k_, v in worst.items() if not v <= TOL}
+    assert not bad, bad
+
+
+def test_large_workload_sampled(capsys):
+    """`large` (50 M vertices, 868 M operator entries, directed, 3-layer GCN, k = 64) as bench.py
+    runs it.  Tensors stay on the device (about 200 GB); the test fetches only what a check needs:
+    rows of sampled vertices and of their in- and out-neighbours, sampled columns, and whole
+    tensors chunk by chunk for the loss and the weight-gradient reductions."""
+    import psutil
+    import torch
+    if os.environ.get("GNNMI_TEST_LARGE") != "1":
+        pytest.skip("seven minutes (three of them input generation): set GNNMI_TEST_LARGE=1 to run")
+    if psutil.virtual_memory().available < 120 * 2 ** 30:
+        pytest.skip("needs ~80 GB of free host memory")
+    if torch.cuda.get_device_properties(0).total_memory < 250 * 2 ** 30:
+        pytest.skip("needs 250 GB of device memory")
+    from oracle import fullgraph as og
+    from paper_2605_11517_amd import Session
+    from synth import features, glorot_weights, labels_and_mask, make_config
+
+    def say(msg):
+        with capsys.disabled():
+            print("[large %.0fs] %s" % (time.time() - t0, msg), flush=True)
+
+    t0 = time.time()
+    cfg, rowptr, colidx = make_config("large")
+    n, dims = cfg["n"], cfg["dims"]
+    assert cfg["self_loops"] and len(dims) == 4
+    X = features(n, dims[0], cfg["seed"])
+    y, m = labels_and_mask(n, dims[-1], cfg["train_frac"], cfg["seed"])
+    w = glorot_weights(dims, cfg["seed"], sage=False, bias_scale=0.05)
+    say("inputs ready: n=%d entries=%d" % (n, rowptr[-1]))
+    s = Session("gcn", dims, rowptr, colidx, cfg["k"], cfg["part"], cfg["seed"], X, w, y, m,
+                layer_order="auto", progress=say)
+    assert [s.ctx.layer_is_transform_first(l) for l in (1, 2, 3)] == [False, True, True]
+    loss = s.epoch()
+    torch.cuda.synchronize()
+    say("GPU epoch done, loss %.6f" % loss)
+    order = s.ctx.get_order()[0].astype(np.int64)        # library row i holds original vertex order[i]
+    pos = np.empty(n, dtype=np.int64)
+    pos[order] = np.arange(n, dtype=np.int64)
+    W = [np.asarray(l["W"], dtype=np.float64) for l in w]
+    b = [np.asarray(l["b"], dtype=np.float64) for l in w]
+    feat_act = [s.feat] + s.act                          # device tensors, library order
+
+    def rows(dev_tensor, verts):
+        """Rows of original vertices `verts` as fp64."""
+        idx = torch.from_numpy(pos[np.asarray(verts, dtype=np.int64)]).to(dev_tensor.device)
+        return dev_tensor[idx].cpu().numpy().astype(np.float64)
+
+    def columns(dev_tensor, cols):
+        """Columns `cols` of every vertex, original order, fp64."""
+        c = dev_tensor[:, torch.from_numpy(np.asarray(cols, dtype=np.int64)).to(dev_tensor.device)].cpu().numpy()
+        out = np.empty(c.shape, dtype=np.float64)
+        out[order] = c
+        return out
+
+    CH = 1 << 21
+
+    def at_times(dev_tensor, G):
+        """dev_tensor^T G with G in original order: fetched and multiplied by row chunks."""
+        acc = np.zeros((dev_tensor.shape[1], G.shape[1]))
+        for r0 in range(0, n, CH):
+            a = dev_tensor[r0:r0 + CH].cpu().numpy().astype(np.float64)
+            acc += a.T @ G[order[r0:r0 + CH]]
+        return acc
+
+    # the operator by its definition: deg(v) = row length (the CSR holds the self-loops),
+    # entry weight 1 / sqrt(deg(u) deg(v))
+    deg = np.diff(rowptr).astype(np.float64)
+    inv = 1.0 / np.sqrt(deg)
+    rng = np.random.default_rng(13)
+    V = np.unique(np.concatenate([rng.choice(n, 256, replace=False), np.argsort(deg)[-4:]]))
+    # out-edges of the sampled vertices: entries whose column is sampled, with their rows
+    lut = np.zeros(n, dtype=bool)
+    lut[V] = True
+    ent = np.flatnonzero(lut[colidx])
+    ent_src = colidx[ent].astype(np.int64)
+    ent_dst = np.searchsorted(rowptr, ent, side="right") - 1
+    del lut
+    say("%d sampled vertices, %d in-entries, %d out-entries"
+        % (len(V), int(deg[V].sum()), len(ent)))
+
+    worst = {}
+    # forward rows, each layer from the path's own previous activations
+    for l in (1, 2, 3):
+        ref = []
+        for v in V:
+            u = colidx[rowptr[v]:rowptr[v + 1]].astype(np.int64)
+            z = (rows(feat_act[l - 1], u) * inv[u][:, None]).sum(axis=0) * inv[v]
+            r = z @ W[l - 1] + b[l - 1]
+            ref.append(np.maximum(r, 0.0) if l < 3 else r)
+        worst["act[%d] rows" % (l - 1)] = rel_err(rows(feat_act[l], V), np.array(ref))
+    say("forward rows checked")
+
+    # loss and its gradient over all rows, chunk by chunk in library order
+    y_lib, m_lib = y[order], m[order]
+    n_train = int(np.count_nonzero(m))
+    lsum, gerr, gmax = 0.0, 0.0, 0.0
+    for r0 in range(0, n, CH):
+        logits = s.act[2][r0:r0 + CH].cpu().numpy()
+        cnt = int(np.count_nonzero(m_lib[r0:r0 + CH]))
+        if cnt == 0:
+            continue
+        lc, gc = og.loss(logits, y_lib[r0:r0 + CH], m_lib[r0:r0 + CH])
+        lsum += lc * cnt
+        gc *= cnt / n_train
+        got = s.gact[2][r0:r0 + CH].cpu().numpy()
+        gerr = max(gerr, float(np.abs(got - gc).max()))
+        gmax = max(gmax, float(np.abs(gc).max()))
+    assert abs(loss - lsum / n_train) <= TOL * abs(lsum / n_train), (loss, lsum / n_train)
+    worst["gact[2]"] = gerr / gmax
+    say("loss and its gradient checked")
+
+    def dY_rows(l, verts):
+        """Rows of dLoss/d(pre-activation) of layer l."""
+        g = rows(s.gact[l - 1], verts)
+        return g if l == 3 else np.where(rows(s.act[l - 1], verts) > 0, g, 0.0)
+
+    def dY_columns(l, cols):
+        g = columns(s.gact[l - 1], cols)
+        return g if l == 3 else np.where(columns(s.act[l - 1], cols) > 0, g, 0.0)
+
+    # transform-first layers 3 and 2: grad H = S^T dY, grad W = A^{l-1 T} grad H,
+    # grad A^{l-1} = grad H W^T; rows of S^T from the sampled vertices' out-entries
+    for l in (3, 2):
+        d = dY_rows(l, ent_dst) * (inv[ent_src] * inv[ent_dst])[:, None]
+        GH = np.zeros((len(V), dims[l]))
+        np.add.at(GH, np.searchsorted(V, ent_src), d)
+        worst["gact[%d] rows" % (l - 2)] = rel_err(rows(s.gact[l - 2], V), GH @ W[l - 1].T)
+        J = np.sort(rng.choice(dims[l], 8, replace=False))
+        dYJ = dY_columns(l, J)
+        GJ = og.aggregate("gcn", rowptr, colidx, dYJ, transpose=True)
+        worst["gW[%d] cols" % (l - 1)] = rel_err(s.gw[3 * (l - 1)][:, torch.from_numpy(J).to(s.dev)].cpu().numpy(),
+                                                 at_times(feat_act[l - 1], GJ))
+        worst["gb[%d] cols" % (l - 1)] = rel_err(s.gw[3 * (l - 1) + 2].cpu().numpy()[J], dYJ.sum(axis=0))
+        del dYJ, GJ
+        say("layer %d checked" % l)
+    # aggregate-first layer 1: grad W = (S X)^T dY = X^T (S^T dY)
+    J = np.sort(rng.choice(dims[1], 8, replace=False))
+    dYJ = dY_columns(1, J)
+    GJ = og.aggregate("gcn", rowptr, colidx, dYJ, transpose=True)
+    worst["gW[0] cols"] = rel_err(s.gw[0][:, torch.from_numpy(J).to(s.dev)].cpu().numpy(), at_times(s.feat, GJ))
+    worst["gb[0] cols"] = rel_err(s.gw[2].cpu().numpy()[J], dYJ.sum(axis=0))
     say("worst relative errors: " + ", ".join("%s=%.2g" % kv for kv in sorted(worst.items())))
     bad = {k_: v for k_, v in worst.items() if not v <= TOL}
     assert not bad, bad
