@@ -280,7 +280,8 @@ class Context:
         return [float(losses[i]) for i in range(epochs)]
 
     def set_profiling(self, enabled):
-        self._check(self.lib.gnn_set_profiling(self.h, 1 if enabled else 0))
+        """False/0 off, True/1 every kernel class, 2 the aggregation kernels only."""
+        self._check(self.lib.gnn_set_profiling(self.h, int(enabled)))
 
     def get_stream_stats(self):
         st = StreamStats()

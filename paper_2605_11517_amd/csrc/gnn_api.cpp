@@ -1239,8 +1239,8 @@ gnn_status gnn_train(gnn_ctx* c, const gnn_optimizer* opt, int32_t epochs, int64
 
 gnn_status gnn_set_profiling(gnn_ctx* c, int32_t enabled)
 {
-    if (!c) return GNN_EINVAL;
-    c->prof = enabled != 0;
+    if (!c || enabled < 0 || enabled > 2) return GNN_EINVAL;
+    c->prof = enabled;
     c->events_used = 0;
     return GNN_OK;
 }

@@ -104,7 +104,7 @@ struct gnn_ctx {
     bool loss_done = false;
     gnnmi::StreamEngine* stream_engine = nullptr;
     // profiling
-    bool prof = false;
+    int prof = 0;                       // 0 off, 1 every kernel class, 2 the aggregation classes only
     std::vector<hipEvent_t> events;
     std::vector<int> event_class;
     size_t events_used = 0;
@@ -136,13 +136,16 @@ namespace gnnmi {
 struct Timed {
     gnn_ctx* c;
     hipStream_t s;
-    Timed(gnn_ctx* ctx, hipStream_t st, int cls) : c(ctx), s(st)
+    bool on;
+    Timed(gnn_ctx* ctx, hipStream_t st, int cls)
+        : c(ctx), s(st),
+          on(ctx->prof == 1 || (ctx->prof == 2 && (cls == GNN_K_SPMM || cls == GNN_K_SPMM_T)))
     {
-        if (c->prof) mark(cls);
+        if (on) mark(cls);
     }
     ~Timed()
     {
-        if (c->prof) mark(-1);
+        if (on) mark(-1);
     }
     void mark(int cls)
     {

@@ -580,3 +580,42 @@ def test_graph_attention_epoch_matches_oracle(name, dims, k, mode):
     for key in ("act", "gact", "gW", "gWs", "gb"):
         for a, b in zip(r1[key], r2[key]):
             assert np.array_equal(a, b), key
+
+
+# ----------------------------------------------------------------------------------------
+# measurement hooks
+# ----------------------------------------------------------------------------------------
+def test_profiling_modes_leave_results_alone_and_agree_on_launch_counts():
+    say("case profiling modes")
+    from paper_2605_11517_amd import Session
+    from paper_2605_11517_amd.binding import GnnError
+    cfg, rowptr, colidx = make_config("mini_sage")
+    n, dims = cfg["n"], cfg["dims"]
+    X = features(n, dims[0], cfg["seed"])
+    y, m = labels_and_mask(n, dims[-1], cfg["train_frac"], cfg["seed"])
+    w = glorot_weights(dims, cfg["seed"], sage=True, bias_scale=0.05)
+    s = Session("sage", dims, rowptr, colidx, 5, "lp", cfg["seed"], X, w, y, m)
+    loss = s.epoch()
+    ref = s.results()
+    prof = {}
+    for mode in (1, 2, 0):
+        s.ctx.set_profiling(mode)
+        assert s.epoch() == loss
+        got = s.results()
+        for key in ("act", "gact", "gW", "gWs", "gb"):
+            for a, b in zip(got[key], ref[key]):
+                assert np.array_equal(a, b), (mode, key)
+        prof[mode] = s.ctx.get_profile()
+    L = len(dims) - 1
+    # every class bracketed: one aggregation per (layer, partition) forward and again for the
+    # recompute, one transposed aggregation per partition of the layers above the first
+    assert prof[1]["spmm"][1] == 2 * L * 5 and prof[1]["spmm_t"][1] == (L - 1) * 5
+    assert prof[1]["gather"][1] > 0 and prof[1]["gemm_fwd"][1] > 0
+    # aggregation only: the same launch counts there, nothing elsewhere
+    for name, (ms, launches) in prof[2].items():
+        if name in ("spmm", "spmm_t"):
+            assert launches == prof[1][name][1] and ms > 0
+        else:
+            assert launches == 0 and ms == 0.0, name
+    with pytest.raises(GnnError):
+        s.ctx.set_profiling(3)
