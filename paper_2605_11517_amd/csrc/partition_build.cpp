@@ -12,6 +12,8 @@
 //     appendix).
 #include <algorithm>
 #include <atomic>
+#include <cstdio>
+#include <chrono>
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
@@ -174,11 +176,15 @@ struct PrefDevice {
     int32_t *part = nullptr, *first = nullptr, *second = nullptr;
     int64_t* sizes = nullptr;
     unsigned long long* frac = nullptr;
+    // pinned host mirrors of the three per-vertex arrays that cross the link every iteration
+    int32_t *host_part = nullptr, *host_first = nullptr, *host_second = nullptr;
     ~PrefDevice()
     {
         for (void* p : {(void*)rowptr, (void*)colidx, (void*)part, (void*)first, (void*)second,
                         (void*)sizes, (void*)frac})
             if (p) (void)hipFree(p);
+        for (void* p : {(void*)host_part, (void*)host_first, (void*)host_second})
+            if (p) (void)hipHostFree(p);
     }
 };
 struct HipFailure {
@@ -207,12 +213,21 @@ void assign_switching(int64_t n, const int64_t* rowptr, const int32_t* colidx, i
         PART_HIP(hipMalloc((void**)&D.second, (size_t)n * 4));
         PART_HIP(hipMalloc((void**)&D.sizes, (size_t)k * 8));
         PART_HIP(hipMalloc((void**)&D.frac, 8));
+        const size_t vbytes = (size_t)std::max<int64_t>(1, n) * 4;
+        PART_HIP(hipHostMalloc((void**)&D.host_part, vbytes, hipHostMallocDefault));
+        PART_HIP(hipHostMalloc((void**)&D.host_first, vbytes, hipHostMallocDefault));
+        PART_HIP(hipHostMalloc((void**)&D.host_second, vbytes, hipHostMallocDefault));
         PART_HIP(hipMemcpy(D.rowptr, rowptr, (size_t)(n + 1) * 8, hipMemcpyHostToDevice));
         if (nnz > 0) PART_HIP(hipMemcpy(D.colidx, colidx, (size_t)nnz * 4, hipMemcpyHostToDevice));
     }
     const int nt = worker_count();
     const int64_t cap = ((int64_t)11 * n) / ((int64_t)10 * k);
-    std::vector<int32_t> first((size_t)n), second((size_t)n);
+    // preferences of every vertex: pinned when the device writes them, plain vectors otherwise
+    std::vector<int32_t> first_store((size_t)(on_device ? 0 : n)), second_store((size_t)(on_device ? 0 : n));
+    int32_t* const first = on_device ? D.host_first : first_store.data();
+    int32_t* const second = on_device ? D.host_second : second_store.data();
+    if (on_device)
+        parallel_for(n, 1 << 16, [&](int, int64_t v) { D.host_part[v] = part[(size_t)v]; });
     std::vector<int64_t> sizes((size_t)k);
     std::vector<std::vector<int64_t>> cnt((size_t)nt, std::vector<int64_t>((size_t)k, 0));
     std::vector<std::vector<int32_t>> touched((size_t)nt);
@@ -224,19 +239,47 @@ void assign_switching(int64_t n, const int64_t* rowptr, const int32_t* colidx, i
     __int128 prev_q = 0;
     int32_t streak = 0;
 
+    // GNNMI_PART_TIMING=1: seconds spent per phase, summed over the iterations, on stderr
+    const bool timing = std::getenv("GNNMI_PART_TIMING") && std::atoi(std::getenv("GNNMI_PART_TIMING")) != 0;
+    double t_sizes = 0, t_pref = 0, t_select = 0, t_apply = 0;
+    auto now = [] { return std::chrono::duration<double>(std::chrono::steady_clock::now().time_since_epoch()).count(); };
+    struct Report {
+        const bool on; const double &a, &b, &c, &d; const SwitchingInfo& info;
+        ~Report()
+        {
+            if (on)
+                std::fprintf(stderr, "switching partitioner: %d iterations; sizes %.3f s, preferences %.3f s, "
+                                     "selection %.3f s, moves %.3f s\n", info.iterations, a, b, c, d);
+        }
+    } report{timing, t_sizes, t_pref, t_select, t_apply, info};
+
     for (int32_t it = 0;; ++it) {
+        double t0 = now();
         std::fill(sizes.begin(), sizes.end(), 0);
-        for (int64_t v = 0; v < n; ++v) sizes[(size_t)part[(size_t)v]]++;
+        if ((int64_t)k <= 4096 && n >= ((int64_t)1 << 20)) {
+            std::vector<std::vector<int64_t>> part_sizes((size_t)nt, std::vector<int64_t>((size_t)k, 0));
+            parallel_for(nchunks, 16, [&](int tid, int64_t ch) {
+                auto& ps = part_sizes[(size_t)tid];
+                const int64_t hi = std::min(n, (ch + 1) * kChunk);
+                for (int64_t v = ch * kChunk; v < hi; ++v) ps[(size_t)part[(size_t)v]]++;
+            });
+            for (auto& ps : part_sizes)
+                for (int32_t j = 0; j < k; ++j) sizes[(size_t)j] += ps[(size_t)j];
+        } else {
+            for (int64_t v = 0; v < n; ++v) sizes[(size_t)part[(size_t)v]]++;
+        }
+        t_sizes += now() - t0;
+        t0 = now();
         // step 1 on the current state, together with the objective of that state
         unsigned long long device_frac = 0;
         if (on_device) {
-            PART_HIP(hipMemcpy(D.part, part.data(), (size_t)n * 4, hipMemcpyHostToDevice));
+            PART_HIP(hipMemcpy(D.part, D.host_part, (size_t)n * 4, hipMemcpyHostToDevice));
             PART_HIP(hipMemcpy(D.sizes, sizes.data(), (size_t)k * 8, hipMemcpyHostToDevice));
             PART_HIP(hipMemset(D.frac, 0, 8));
             launch_switch_pref(n, D.rowptr, D.colidx, D.part, D.sizes, k, D.first, D.second, D.frac, nullptr);
             PART_HIP(hipGetLastError());
-            PART_HIP(hipMemcpy(first.data(), D.first, (size_t)n * 4, hipMemcpyDeviceToHost));
-            PART_HIP(hipMemcpy(second.data(), D.second, (size_t)n * 4, hipMemcpyDeviceToHost));
+            PART_HIP(hipMemcpy(first, D.first, (size_t)n * 4, hipMemcpyDeviceToHost));
+            PART_HIP(hipMemcpy(second, D.second, (size_t)n * 4, hipMemcpyDeviceToHost));
             PART_HIP(hipMemcpy(&device_frac, D.frac, 8, hipMemcpyDeviceToHost));
             std::fill(frac_sum.begin(), frac_sum.end(), 0);
         } else {
@@ -285,6 +328,8 @@ void assign_switching(int64_t n, const int64_t* rowptr, const int32_t* colidx, i
             frac_sum[(size_t)ch] = fsum;
         });
         }
+        t_pref += now() - t0;
+        t0 = now();
         __int128 total = (__int128)n * kFracOne + device_frac;
         for (int64_t ch = 0; ch < nchunks; ++ch) total += frac_sum[(size_t)ch];
         __int128 sq = 0;
@@ -302,10 +347,52 @@ void assign_switching(int64_t n, const int64_t* rowptr, const int32_t* colidx, i
 
         // step 2: per range, per target partition, the largest second-preference group moves
         std::atomic<int64_t> moved{0};
+        // Group sizes come from a (first, second) histogram per range when k is small enough for
+        // one (k x (k + 1) counters per range); otherwise the candidates are sorted.  Both pick
+        // the same group and the same vertices.
+        const char* force_sort = std::getenv("GNNMI_SWITCH_SORT");
+        const bool by_histogram = (int64_t)k * (k + 1) <= ((int64_t)1 << 20) &&
+                                  !(force_sort && std::atoi(force_sort) != 0);
         parallel_for(kSwitchingWorkers, 1, [&](int, int64_t w) {
+            const int64_t lo = (w * n) / kSwitchingWorkers, hi = ((w + 1) * n) / kSwitchingWorkers;
+            auto room_of = [&](int32_t j) {
+                const int64_t rc = std::max<int64_t>(0, cap - sizes[(size_t)j]);
+                return rc / kSwitchingWorkers + (w < rc % kSwitchingWorkers ? 1 : 0);
+            };
+            int64_t local_moved = 0;
+            if (by_histogram) {
+                const int64_t k1 = (int64_t)k + 1;                 // second preference -1 ("none") .. k-1
+                std::vector<int64_t> hist((size_t)(k * k1), 0);
+                for (int64_t v = lo; v < hi; ++v)
+                    if (first[(size_t)v] != part[(size_t)v])
+                        ++hist[(size_t)(first[(size_t)v] * k1 + second[(size_t)v] + 1)];
+                std::vector<int32_t> chosen((size_t)k, -3);        // second preference of the moving group
+                std::vector<int64_t> take((size_t)k, 0);
+                for (int32_t j = 0; j < k; ++j) {
+                    int64_t best_len = 0;
+                    int32_t best_second = -3;
+                    for (int64_t t = 0; t < k1; ++t)                 // ascending second: first wins ties
+                        if (hist[(size_t)(j * k1 + t)] > best_len) {
+                            best_len = hist[(size_t)(j * k1 + t)];
+                            best_second = (int32_t)t - 1;
+                        }
+                    chosen[(size_t)j] = best_second;
+                    take[(size_t)j] = std::min(best_len, room_of(j));
+                }
+                // first[] of a mover is its new home; the assignment itself changes below
+                for (int64_t v = lo; v < hi; ++v) {
+                    const int32_t j = first[(size_t)v];
+                    if (j == part[(size_t)v] || second[(size_t)v] != chosen[(size_t)j] || take[(size_t)j] == 0)
+                        continue;
+                    second[(size_t)v] = -2;
+                    --take[(size_t)j];
+                    ++local_moved;
+                }
+                moved += local_moved;
+                return;
+            }
             auto& L = cands[(size_t)w];
             L.clear();
-            const int64_t lo = (w * n) / kSwitchingWorkers, hi = ((w + 1) * n) / kSwitchingWorkers;
             for (int64_t v = lo; v < hi; ++v)
                 if (first[(size_t)v] != part[(size_t)v])
                     L.push_back({first[(size_t)v], second[(size_t)v], (int32_t)v});
@@ -314,7 +401,6 @@ void assign_switching(int64_t n, const int64_t* rowptr, const int32_t* colidx, i
                 if (a.second != b.second) return a.second < b.second;
                 return a.v < b.v;
             });
-            int64_t local_moved = 0;
             size_t i = 0;
             while (i < L.size()) {
                 const int32_t j = L[i].first;
@@ -326,9 +412,7 @@ void assign_switching(int64_t n, const int64_t* rowptr, const int32_t* colidx, i
                     if (e - g > best_len) { best_len = e - g; best_lo = g; }   // ascending second: first wins ties
                     g = e;
                 }
-                const int64_t rc = std::max<int64_t>(0, cap - sizes[(size_t)j]);
-                const int64_t room = rc / kSwitchingWorkers + (w < rc % kSwitchingWorkers ? 1 : 0);
-                const size_t take = (size_t)std::min<int64_t>((int64_t)best_len, room);
+                const size_t take = (size_t)std::min<int64_t>((int64_t)best_len, room_of(j));
                 // first[] of a mover is its new home; the assignment itself changes below
                 for (size_t t = best_lo; t < best_lo + take; ++t) second[(size_t)L[t].v] = -2;
                 local_moved += (int64_t)take;
@@ -336,10 +420,16 @@ void assign_switching(int64_t n, const int64_t* rowptr, const int32_t* colidx, i
             }
             moved += local_moved;
         });
+        t_select += now() - t0;
+        t0 = now();
         if (moved.load() == 0) break;   // a fixed point: every further iteration repeats it
         parallel_for(n, 1 << 16, [&](int, int64_t v) {
-            if (second[(size_t)v] == -2) part[(size_t)v] = first[(size_t)v];
+            if (second[(size_t)v] == -2) {
+                part[(size_t)v] = first[(size_t)v];
+                if (on_device) D.host_part[v] = first[(size_t)v];
+            }
         });
+        t_apply += now() - t0;
     }
 }
 

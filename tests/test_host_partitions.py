@@ -168,6 +168,23 @@ def test_switching_assignment_does_not_depend_on_the_thread_count(monkeypatch):
     assert sizes.max() <= (11 * cfg["n"]) // (10 * 6)
 
 
+@pytest.mark.parametrize("name,k,seed", [("tiny", 6, 21), ("mini_sage", 37, 3), ("mini_gcn_directed", 2, 9)])
+def test_switching_group_selection_by_histogram_equals_selection_by_sorting(monkeypatch, name, k, seed):
+    """The moving group of every (range, target partition) is found from a histogram of
+    (first, second) preferences when k is small and from sorted candidates otherwise; the two
+    must pick the same vertices, and both must equal the oracle's assignment."""
+    cfg, rowptr, colidx = make_config(name)
+    got = []
+    for force in ("0", "1"):
+        monkeypatch.setenv("GNNMI_SWITCH_SORT", force)
+        ctx = Context(cfg["model"], cfg["dims"])
+        ctx.build_partitions(rowptr, colidx, k, "switching", seed)
+        got.append((ctx.get_partition()[0].copy(), ctx.get_partitioner_history()[0]))
+    assert got[0][1] == got[1][1] and np.array_equal(got[0][0], got[1][0])
+    want, info = op.assign_switching(rowptr, colidx, k, seed, workers=16)
+    assert np.array_equal(got[0][0], want)
+
+
 def test_partition_order_follows_shared_blocks():
     k, per = 9, 12
     rowptr, colidx, part, label = ring_of_blocks(k, per, seed=4)
