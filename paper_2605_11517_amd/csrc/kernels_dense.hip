@@ -256,22 +256,26 @@ __global__ __launch_bounds__(kBlock) void k_act_bwd_bf16(const float* __restrict
     }
 }
 
-// gb[c] += sum_b partial[b, c]: a block owns 32 columns; its 8 row groups walk the partial rows
-// 8 apart and are combined through LDS in a fixed order.
-__global__ __launch_bounds__(kBlock) void k_colsum_finish(const float* __restrict__ partial,
-                                                          int64_t nblocks, int32_t d,
-                                                          float* __restrict__ gb)
+// gb[c] += sum_b partial[b, c]: a block of 1024 threads owns 32 columns; its 32 row groups walk
+// the partial rows 32 apart, eight loads in flight each, and are combined through LDS in a fixed
+// order (a partition of 8*10^5 rows leaves 3*10^3 partial rows: with 8 row groups the walk took
+// 48 us, bound by the latency of its ~100 dependent steps).
+constexpr int kFinishGroups = 32;
+__global__ __launch_bounds__(32 * kFinishGroups) void k_colsum_finish(const float* __restrict__ partial,
+                                                                      int64_t nblocks, int32_t d,
+                                                                      float* __restrict__ gb)
 {
-    __shared__ float sm[8][32];
+    __shared__ float sm[kFinishGroups][32];
     const int tx = threadIdx.x % 32, ty = threadIdx.x / 32;
     const int32_t c = blockIdx.x * 32 + tx;
     float s = 0.f;
     if (c < d) {
-        constexpr int U = 4;
-        for (int64_t b = ty; b < nblocks; b += 8 * U) {
+        constexpr int U = 8;
+        for (int64_t b = ty; b < nblocks; b += kFinishGroups * U) {
             float x[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) x[u] = b + 8 * u < nblocks ? partial[(b + 8 * u) * d + c] : 0.f;
+            for (int u = 0; u < U; ++u)
+                x[u] = b + kFinishGroups * u < nblocks ? partial[(b + kFinishGroups * u) * d + c] : 0.f;
 #pragma unroll
             for (int u = 0; u < U; ++u) s += x[u];
         }
@@ -279,7 +283,7 @@ __global__ __launch_bounds__(kBlock) void k_colsum_finish(const float* __restric
     sm[ty][tx] = s;
     __syncthreads();
     if (ty == 0 && c < d) {
-        for (int q = 1; q < 8; ++q) s += sm[q][tx];
+        for (int q = 1; q < kFinishGroups; ++q) s += sm[q][tx];
         gb[c] += s;
     }
 }
@@ -483,7 +487,7 @@ void launch_act_bwd(const float* g, const float* act, float* dy, int64_t rows, i
         hipLaunchKernelGGL(k_act_bwd, dim3((unsigned)blocks), dim3(kBlock), 0, s, g, act, dy, rows, d,
                            partial, scale);
     if (gb)
-        hipLaunchKernelGGL(k_colsum_finish, dim3((unsigned)((d + 31) / 32)), dim3(kBlock),
+        hipLaunchKernelGGL(k_colsum_finish, dim3((unsigned)((d + 31) / 32)), dim3(32 * kFinishGroups),
                            0, s, (const float*)partial, blocks, d, gb);
 }
 
@@ -496,7 +500,7 @@ void launch_act_bwd_bf16(const float* g, const void* act, void* dy, int64_t rows
     hipLaunchKernelGGL(k_act_bwd_bf16, dim3((unsigned)blocks), dim3(kBlock), 0, s, g,
                        (const uint16_t*)act, (uint16_t*)dy, rows, d, partial, scale);
     if (gb)
-        hipLaunchKernelGGL(k_colsum_finish, dim3((unsigned)((d + 31) / 32)), dim3(kBlock), 0, s,
+        hipLaunchKernelGGL(k_colsum_finish, dim3((unsigned)((d + 31) / 32)), dim3(32 * kFinishGroups), 0, s,
                            (const float*)partial, blocks, d, gb);
 }
 
@@ -517,7 +521,7 @@ void launch_dropout(void* a, int is_bf16, const int32_t* orig_of_row, int64_t ro
 void launch_colsum_finish(const float* partial, int64_t nblocks, int32_t d, float* out, hipStream_t s)
 {
     if (nblocks <= 0 || d <= 0) return;
-    hipLaunchKernelGGL(k_colsum_finish, dim3((unsigned)((d + 31) / 32)), dim3(kBlock), 0, s, partial, nblocks,
+    hipLaunchKernelGGL(k_colsum_finish, dim3((unsigned)((d + 31) / 32)), dim3(32 * kFinishGroups), 0, s, partial, nblocks,
                        d, out);
 }
 
