@@ -153,6 +153,13 @@ void compute_workspace(gnn_ctx* c)
         w.gh = c->model == GNN_GAT ? take(M.n * hp) : w.h;
         w.wpad = take(2 * din * hp);
     }
+    w.dyall = -1;
+    if (c->model == GNN_SAGE_MEAN && !c->bf16()) {
+        int64_t dyw = 0;
+        for (int32_t l = 2; l < L; ++l)
+            if (c->transform_first(l)) dyw = std::max<int64_t>(dyw, c->padded(l));
+        if (dyw > 0) w.dyall = take(M.n * dyw);
+    }
     if (c->model == GNN_GAT) {
         w.ssrc = take(M.n);
         w.sdst = take(M.n);
@@ -556,6 +563,10 @@ static void xf_aggregate_bwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s
         }
         return;
     }
+    // a hidden GraphSAGE layer keeps its (padded) dY rows for the second sweep
+    float* keep = c->model == GNN_SAGE_MEAN && layer >= 2 && layer < L && c->ws.dyall >= 0
+                      ? (float*)(c->scratch + c->ws.dyall) + r0 * dp : nullptr;
+    if (keep && dp == dout) dYbuf = keep;
     const float* dY = g_own;
     {
         Timed t(c, s, GNN_K_ACT_BWD);
@@ -572,7 +583,7 @@ static void xf_aggregate_bwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s
     const float* dYp = dY;
     if (dp != dout) {
         Timed t(c, s, GNN_K_OTHER);
-        float* pad = (float*)(c->scratch + c->ws.dz);
+        float* pad = keep ? keep : (float*)(c->scratch + c->ws.dz);
         launch_pad_rows(pad, dY, np, dout, dp, s);
         dYp = pad;
     }
@@ -582,10 +593,11 @@ static void xf_aggregate_bwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s
             launch_gemm_tn(in_own, din, dYp, dp, c->gw[(size_t)3 * (layer - 1) + 1], dout, din, dout, np,
                            (float*)(c->scratch + c->ws.partial), s);
         }
-        if (layer >= 2 && layer < L) {
+        if (layer >= 2 && layer < L && !keep) {
             // self term: grad A^{l-1}_own = dY W_s^T (the first thing written to these rows),
-            // contracted over the padded width.  The output layer has dY = grad A^L at hand in
-            // the second sweep as well and takes both terms of grad A^{l-1} in one contraction there.
+            // contracted over the padded width.  (Not reached while the workspace keeps dY of every
+            // partition: then the second sweep takes both terms of grad A^{l-1} in one contraction,
+            // as the output layer does with dY = grad A^L.)
             const PaddedW ws = padded_weight(c, layer, 1);
             Timed t(c, s, GNN_K_GEMM_DZ);
             GemmEpilogue ep;
@@ -982,10 +994,13 @@ gnn_status gnn_layer_transform_bwd(gnn_ctx* c, int32_t layer, int32_t p, void* s
         launch_gemm_tn(in_own, din, gH, dp, c->gw[(size_t)3 * (layer - 1)], dout, din, dout, np,
                        (float*)(c->scratch + c->ws.partial), s);
     }
-    if (layer >= 2 && layer == c->L && c->model == GNN_SAGE_MEAN) {
-        // grad A^{l-1}_own = grad H_p W^T + dY_p W_s^T in one pass over the result (dY_p = grad A^L_p)
-        const float* dY = c->gact[(size_t)layer - 1] + r0 * dout;
-        if (dp != dout) {
+    const bool kept = c->model == GNN_SAGE_MEAN && layer >= 2 && layer < c->L && c->ws.dyall >= 0;
+    if (layer >= 2 && (layer == c->L || kept) && c->model == GNN_SAGE_MEAN) {
+        // grad A^{l-1}_own = grad H_p W^T + dY_p W_s^T in one pass over the result: the output
+        // layer's dY_p is grad A^L_p, a hidden layer's padded dY_p was kept by the first sweep
+        const float* dY = kept ? (const float*)(c->scratch + c->ws.dyall) + r0 * dp
+                               : c->gact[(size_t)layer - 1] + r0 * dout;
+        if (!kept && dp != dout) {
             Timed t(c, s, GNN_K_OTHER);
             float* pad = (float*)(c->scratch + c->ws.dz);
             launch_pad_rows(pad, dY, np, dout, dp, s);

@@ -42,6 +42,10 @@ struct Workspace {  // byte offsets into `scratch`
     int64_t h = 0, gh = 0;     // transform-first layers: H = A W and its gradient, n x padded width
     int64_t wpad = 0;          // and copies of W, W_s with rows padded to that width (2 x d_in x padded)
     int64_t wt = 0;            // bfloat16 storage: room for one transposed weight matrix
+    // fp32 GraphSAGE with hidden transform-first layers: dY of every partition (n x padded width)
+    // stays until the layer's second sweep, which then takes both terms of grad A^{l-1} in one
+    // contraction instead of writing one and accumulating the other; -1: not needed
+    int64_t dyall = -1;
     // graph attention: per-vertex scores and their gradients, staged boundary scores, per-entry
     // attention weights, edge-wise products, attention weights in transposed order
     int64_t ssrc = 0, sdst = 0, gssrc = 0, gsdst = 0, bs = 0, att = 0, dal = 0, twatt = 0;

@@ -462,6 +462,7 @@ def test_dropout_epoch_and_training_steps_match_oracle(model, dims, dropout):
 @pytest.mark.parametrize("name,dims", [("tiny", None),                      # gcn 64 -> 64 -> 16
                                        ("mini_sage", (24, 32, 12, 7)),      # two narrowing layers, padded width
                                        ("mini_sage", (16, 40, 40, 40, 6)),  # equal widths: saves the recompute
+                                       ("mini_sage", (24, 30, 10, 7)),      # hidden layer with padded rows
                                        ("mini_gcn_directed", (20, 9, 9, 5))])   # layer 1 as well
 def test_transform_first_layers_match_oracle(name, dims):
     say("case transform-first %s %s" % (name, dims))
