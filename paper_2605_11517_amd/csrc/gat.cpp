@@ -129,7 +129,7 @@ void gat_bwd_begin(gnn_ctx* c, int32_t layer, hipStream_t s)
     launch_fill_zero(c->scratch + c->ws.gh, n * (int64_t)c->padded(layer) * 4, s);
     launch_fill_zero(c->scratch + c->ws.gssrc, n * 4, s);
     launch_fill_zero(c->scratch + c->ws.gsdst, n * 4, s);
-    if (layer >= 2) launch_fill_zero(c->gact[(size_t)layer - 2], n * (int64_t)c->dims[(size_t)layer - 1] * 4, s);
+    // grad A^{l-1} needs no initialisation: each of its rows is written once, by grad H_p W^T
 }
 
 void gat_layer_bwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
@@ -213,8 +213,7 @@ void gat_transform_bwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
     }
     if (layer >= 2) {
         Timed t(c, s, GNN_K_GEMM_DZ);
-        GemmEpilogue ep;
-        ep.accumulate = 1;
+        GemmEpilogue ep;                 // the only term of grad A^{l-1}_p: written, not accumulated
         launch_gemm_nt(gHp, v.dp, (const float*)c->w[(size_t)3 * (layer - 1)], v.dout,
                        c->gact[(size_t)layer - 2] + v.r0 * v.din, v.din, v.np, v.din, v.dout, ep, s);
     }
