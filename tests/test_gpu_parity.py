@@ -330,6 +330,41 @@ def test_streaming_schedule_is_bit_identical_to_resident(case):
     assert e.value.status == 5
 
 
+def test_streaming_and_resident_epochs_on_a_created_stream():
+    """The caller's compute stream need not be the null stream: on a stream created by the caller
+    (which orders itself against nothing implicitly) both schedules give the bits they give on
+    the null stream, also when epochs on the two kinds of stream alternate."""
+    say("case epochs on a created stream")
+    import torch
+    from paper_2605_11517_amd import Session
+    cfg, rowptr, colidx = make_config("mini_sage")
+    n, dims = cfg["n"], cfg["dims"]
+    X, y, m, w = make_inputs(cfg, n)
+    res = Session(cfg["model"], dims, rowptr, colidx, cfg["k"], cfg["part"], cfg["seed"], X, w, y, m)
+    loss = res.epoch()
+    ref = res.results()
+    st = res.ctx.get_stats()
+    rnd = lambda b: (b + 255) // 256 * 256
+    minimum = 4 * rnd(st["max_own"] * max(dims) * 4)
+    stream_s = Session(cfg["model"], dims, rowptr, colidx, cfg["k"], cfg["part"], cfg["seed"], X, w, y, m,
+                       hbm_budget_bytes=int(minimum * 2.5))
+    side = torch.cuda.Stream()
+    for s in (res, stream_s):
+        for rep in range(3):
+            if rep == 1:
+                assert s.epoch() == loss                       # null stream in between
+            else:
+                side.wait_stream(torch.cuda.current_stream())
+                with torch.cuda.stream(side):
+                    assert s.stream == side.cuda_stream
+                    assert s.epoch() == loss
+                torch.cuda.current_stream().wait_stream(side)
+            got = s.results()
+            for key in ("act", "gact", "gW", "gWs", "gb"):
+                for a, b in zip(got[key], ref[key]):
+                    assert np.array_equal(a, b), (s is stream_s, rep, key)
+
+
 def test_streaming_partition_order_reuses_cached_blocks(monkeypatch):
     say("case streaming with the reuse order against the id order")
     from paper_2605_11517_amd import Session
