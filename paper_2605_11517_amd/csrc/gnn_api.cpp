@@ -131,6 +131,7 @@ void compute_workspace(gnn_ctx* c)
     w.dz = take(max_np * din);
     w.dga = take(max_r * din);
     w.partial = take(part);
+    w.partial2 = take(part);
     w.colpart = take(std::max(act_bwd_partial_floats(max_np, (int32_t)dout),
                               gat_rank1_partial_floats(max_np, (int32_t)dout)));
     w.losspart = take(loss_partial_floats(M.n, M.k));
@@ -662,6 +663,8 @@ void gnn_destroy(gnn_ctx* c)
     stream_engine_destroy(c);
     if (c->D.ready) free_device(c->D);
     for (hipEvent_t e : c->events) (void)hipEventDestroy(e);
+    for (hipEvent_t e : c->side_events) (void)hipEventDestroy(e);
+    if (c->side) (void)hipStreamDestroy(c->side);
     delete c;
 }
 
@@ -992,7 +995,7 @@ gnn_status gnn_layer_transform_bwd(gnn_ctx* c, int32_t layer, int32_t p, void* s
     {
         Timed t(c, s, GNN_K_GEMM_DW);
         launch_gemm_tn(in_own, din, gH, dp, c->gw[(size_t)3 * (layer - 1)], dout, din, dout, np,
-                       (float*)(c->scratch + c->ws.partial), s);
+                       (float*)(c->scratch + (c->on_side ? c->ws.partial2 : c->ws.partial)), s);
     }
     const bool kept = c->model == GNN_SAGE_MEAN && layer >= 2 && layer < c->L && c->ws.dyall >= 0;
     if (layer >= 2 && (layer == c->L || kept) && c->model == GNN_SAGE_MEAN) {
@@ -1144,18 +1147,77 @@ gnn_status gnn_epoch(gnn_ctx* c, void* stream, float* loss_out)
         return st;
     }
     gnn_status st;
+    // Overlap (fp32 GCN / GraphSAGE): where an aggregate-first layer l sits below a transform-first
+    // layer l + 1, the contractions of layer l + 1's own sweep (H_p = A_p^l W forward; grad W,
+    // grad A_p^l backward) run on a side stream, partition by partition, beside layer l's gather /
+    // aggregation kernels of the other partitions.  Those contractions touch only rows of
+    // partition p, H / grad H, the padded weight copies, their own weight gradient and a split-K
+    // region of their own; every dependency is an event, and each buffer sees its kernels in the
+    // order of the one-stream schedule, so the results are the same bits.  GNNMI_OVERLAP=0: off.
+    const char* overlap_env = std::getenv("GNNMI_OVERLAP");          // read per epoch: tests flip it
+    bool overlap = !(overlap_env && overlap_env[0] == '0') && !c->bf16() && c->model != GNN_GAT && L >= 2;
+    if (overlap) {
+        bool any = false;
+        for (int32_t l = 1; l < L; ++l) any = any || (!c->transform_first(l) && c->transform_first(l + 1));
+        overlap = any;
+    }
+    if (overlap && !c->side) {
+        if (hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) != hipSuccess) {
+            (void)hipGetLastError();
+            c->side = nullptr;
+            overlap = false;
+        }
+    }
+    if (overlap)
+        while (c->side_events.size() < (size_t)k + 2) {
+            hipEvent_t e;
+            if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) {
+                (void)hipGetLastError();
+                overlap = false;
+                break;
+            }
+            c->side_events.push_back(e);
+        }
+    // layer l aggregates first and layer l + 1 transforms first
+    auto paired = [&](int32_t l) {
+        return overlap && l >= 1 && l < L && !c->transform_first(l) && c->transform_first(l + 1);
+    };
+    // backward: a GraphSAGE output layer with padded rows pads its dY into scratch that layer l's
+    // partitions use as well, so that pair stays on one stream
+    auto paired_bwd = [&](int32_t l) {
+        return paired(l) && !(c->model == GNN_SAGE_MEAN && l + 1 == L && c->padded(L) != c->dims[(size_t)L]);
+    };
+    auto hip_ok = [&](hipError_t e, const char* what) {
+        if (e == hipSuccess) return GNN_OK;
+        return c->fail(GNN_EHIP, std::string(what) + ": " + hipGetErrorString(e));
+    };
+    hipEvent_t* step_event = c->side_events.data();                          // [k]
+    const hipEvent_t fence_main = overlap ? c->side_events[(size_t)k] : nullptr;
+    const hipEvent_t fence_side = overlap ? c->side_events[(size_t)k + 1] : nullptr;
+
     zero_weight_grads(c, s);
     for (int32_t l = 1; l <= L; ++l) {
-        if (c->transform_first(l))
+        if (c->transform_first(l) && !paired(l - 1))
             for (int32_t t = 0; t < k; ++t)
                 if ((st = gnn_layer_transform_fwd(c, l, c->M.sched[(size_t)t], stream)) != GNN_OK) return st;
         for (int32_t t = 0; t < k; ++t) {
             const int32_t p = c->M.sched[(size_t)t];
             if ((st = gnn_gather_boundary(c, l, p, stream)) != GNN_OK) return st;
             if ((st = gnn_layer_fwd(c, l, p, stream)) != GNN_OK) return st;
+            if (paired(l)) {
+                // A_p^l is complete on the caller's stream: layer l + 1 transforms it on the side
+                if ((st = hip_ok(hipEventRecord(step_event[t], s), "hipEventRecord")) != GNN_OK) return st;
+                if ((st = hip_ok(hipStreamWaitEvent(c->side, step_event[t], 0), "hipStreamWaitEvent")) != GNN_OK) return st;
+                if ((st = gnn_layer_transform_fwd(c, l + 1, p, (void*)c->side)) != GNN_OK) return st;
+            }
+        }
+        if (paired(l)) {
+            if ((st = hip_ok(hipEventRecord(fence_side, c->side), "hipEventRecord")) != GNN_OK) return st;
+            if ((st = hip_ok(hipStreamWaitEvent(s, fence_side, 0), "hipStreamWaitEvent")) != GNN_OK) return st;
         }
     }
     if ((st = gnn_loss(c, stream)) != GNN_OK) return st;
+    bool wait_steps = false;          // the partitions of this layer wait for the side stream, step by step
     for (int32_t l = L; l >= 1; --l) {
         const bool xf = c->transform_first(l);
         const bool regather = !xf || c->model == GNN_GAT;
@@ -1165,12 +1227,31 @@ gnn_status gnn_epoch(gnn_ctx* c, void* stream, float* loss_out)
                 if ((st = gnn_layer_transform_fwd(c, l, c->M.sched[(size_t)t], stream)) != GNN_OK) return st;
         for (int32_t t = 0; t < k; ++t) {
             const int32_t p = c->M.sched[(size_t)t];
+            if (wait_steps &&
+                (st = hip_ok(hipStreamWaitEvent(s, step_event[t], 0), "hipStreamWaitEvent")) != GNN_OK)
+                return st;
             if (regather && (st = gnn_gather_boundary(c, l, p, stream)) != GNN_OK) return st;
             if ((st = gnn_layer_bwd(c, l, p, stream)) != GNN_OK) return st;
         }
-        if (xf)
+        wait_steps = false;
+        if (xf && paired_bwd(l - 1)) {
+            // grad H of this layer is complete on the caller's stream: its contractions go to the
+            // side stream, and partition p of layer l - 1 starts when grad A_p^{l-1} is there
+            if ((st = hip_ok(hipEventRecord(fence_main, s), "hipEventRecord")) != GNN_OK) return st;
+            if ((st = hip_ok(hipStreamWaitEvent(c->side, fence_main, 0), "hipStreamWaitEvent")) != GNN_OK) return st;
+            c->on_side = true;
+            for (int32_t t = 0; t < k; ++t) {
+                st = gnn_layer_transform_bwd(c, l, c->M.sched[(size_t)t], (void*)c->side);
+                if (st == GNN_OK) st = hip_ok(hipEventRecord(step_event[t], c->side), "hipEventRecord");
+                if (st != GNN_OK) break;
+            }
+            c->on_side = false;
+            if (st != GNN_OK) return st;
+            wait_steps = true;
+        } else if (xf) {
             for (int32_t t = 0; t < k; ++t)
                 if ((st = gnn_layer_transform_bwd(c, l, c->M.sched[(size_t)t], stream)) != GNN_OK) return st;
+        }
     }
     if ((st = gnn_read_loss(c, stream, loss_out)) != GNN_OK) return st;
     if (c->prof) collect_profile(c);

@@ -46,6 +46,8 @@ struct Workspace {  // byte offsets into `scratch`
     // stays until the layer's second sweep, which then takes both terms of grad A^{l-1} in one
     // contraction instead of writing one and accumulating the other; -1: not needed
     int64_t dyall = -1;
+    // second split-K partial region, for contractions that gnn_epoch runs on its side stream
+    int64_t partial2 = 0;
     // graph attention: per-vertex scores and their gradients, staged boundary scores, per-entry
     // attention weights, edge-wise products, attention weights in transposed order
     int64_t ssrc = 0, sdst = 0, gssrc = 0, gsdst = 0, bs = 0, att = 0, dal = 0, twatt = 0;
@@ -115,6 +117,11 @@ struct gnn_ctx {
     double prof_ms[GNN_K_COUNT] = {0};
     int64_t prof_launches[GNN_K_COUNT] = {0};
     gnn_stream_stats stream_stats{};
+    // gnn_epoch, resident schedule: the contractions of a transform-first layer's own sweep run
+    // on a side stream beside the neighbouring aggregate-first layer's partitions
+    hipStream_t side = nullptr;
+    std::vector<hipEvent_t> side_events;   // per schedule step, plus two fences
+    bool on_side = false;                  // calls made for the side stream take the second partial region
 
     gnn_status fail(gnn_status st, const std::string& msg) const
     {

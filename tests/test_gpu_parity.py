@@ -561,6 +561,44 @@ def test_transform_first_layers_match_oracle(name, dims):
     assert not any(s0.ctx.layer_is_transform_first(l) for l in range(1, L + 1))
 
 
+@pytest.mark.parametrize("name,dims", [("tiny", None),                      # gcn, output layer paired
+                                       ("mini_sage", (24, 30, 10, 7)),      # hidden pair, padded rows
+                                       ("mini_sage", (24, 32, 8)),          # sage output layer without padding
+                                       ("mini_sage", (24, 32, 7)),          # sage output layer, padded: forward pair only
+                                       ("mini_gcn_directed", (20, 24, 9, 9, 5))])
+def test_side_stream_overlap_gives_the_one_stream_bits(monkeypatch, name, dims):
+    """gnn_epoch runs a transform-first layer's contractions on a side stream beside the
+    aggregate-first layer below it; with GNNMI_OVERLAP=0 everything runs on the caller's stream.
+    Same bits, epoch after epoch, also with dropout and optimizer steps in between."""
+    say("case overlap %s %s" % (name, dims))
+    from paper_2605_11517_amd import Session
+    over = {} if dims is None else {"dims": dims}
+    cfg, rowptr, colidx = make_config(name, **over)
+    n, dims, model, k = cfg["n"], cfg["dims"], cfg["model"], cfg["k"]
+    L = len(dims) - 1
+    X, y, m, w = make_inputs(cfg, n)
+    out = {}
+    for flag in ("0", "1"):
+        monkeypatch.setenv("GNNMI_OVERLAP", flag)
+        s = Session(model, dims, rowptr, colidx, k, cfg["part"], cfg["seed"], X, w, y, m, layer_order="auto")
+        xf = [s.ctx.layer_is_transform_first(l) for l in range(1, L + 1)]
+        assert any((not a) and b for a, b in zip(xf, xf[1:])), xf        # there is a pair to overlap
+        losses = [s.epoch(), s.epoch()]
+        r = s.results()
+        losses += s.train(3, optimizer="adam", lr=0.01, dropout=0.3, seed=5)
+        out[flag] = (losses, r, s.results(), s.weights())
+    assert out["0"][0] == out["1"][0]
+    for idx in (1, 2):
+        for key in ("act", "gact", "gW", "gWs", "gb"):
+            for a, b in zip(out["0"][idx][key], out["1"][idx][key]):
+                if a is not None:
+                    assert np.array_equal(a, b), (idx, key)
+    for la, lb in zip(out["0"][3], out["1"][3]):
+        for key in ("W", "Ws", "b"):
+            if la[key] is not None:
+                assert np.array_equal(la[key], lb[key]), key
+
+
 # ----------------------------------------------------------------------------------------
 # graph attention
 # ----------------------------------------------------------------------------------------
