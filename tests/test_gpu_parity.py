@@ -332,24 +332,29 @@ def test_streaming_schedule_is_bit_identical_to_resident(case):
 
 def test_streaming_and_resident_epochs_on_a_created_stream():
     """The caller's compute stream need not be the null stream: on a stream created by the caller
-    (which orders itself against nothing implicitly) both schedules give the bits they give on
-    the null stream, also when epochs on the two kinds of stream alternate."""
+    (which orders itself against nothing implicitly) every schedule gives the bits it gives on
+    the null stream, also when epochs on the two kinds of stream alternate.  The resident
+    session with per-layer order selection also exercises the library's own side stream."""
     say("case epochs on a created stream")
     import torch
     from paper_2605_11517_amd import Session
     cfg, rowptr, colidx = make_config("mini_sage")
     n, dims = cfg["n"], cfg["dims"]
     X, y, m, w = make_inputs(cfg, n)
-    res = Session(cfg["model"], dims, rowptr, colidx, cfg["k"], cfg["part"], cfg["seed"], X, w, y, m)
-    loss = res.epoch()
-    ref = res.results()
+    args = (cfg["model"], dims, rowptr, colidx, cfg["k"], cfg["part"], cfg["seed"], X, w, y, m)
+    res = Session(*args)
     st = res.ctx.get_stats()
     rnd = lambda b: (b + 255) // 256 * 256
     minimum = 4 * rnd(st["max_own"] * max(dims) * 4)
-    stream_s = Session(cfg["model"], dims, rowptr, colidx, cfg["k"], cfg["part"], cfg["seed"], X, w, y, m,
-                       hbm_budget_bytes=int(minimum * 2.5))
+    auto = Session(*args, layer_order="auto")
+    xf = [auto.ctx.layer_is_transform_first(l) for l in range(1, len(dims))]
+    assert any((not a) and b for a, b in zip(xf, xf[1:])), xf
+    sessions = {"resident": res, "resident, order by rows moved": auto,
+                "streaming": Session(*args, hbm_budget_bytes=int(minimum * 2.5))}
     side = torch.cuda.Stream()
-    for s in (res, stream_s):
+    for tag, s in sessions.items():
+        loss = s.epoch()                                       # null stream
+        ref = s.results()
         for rep in range(3):
             if rep == 1:
                 assert s.epoch() == loss                       # null stream in between
@@ -362,7 +367,7 @@ def test_streaming_and_resident_epochs_on_a_created_stream():
             got = s.results()
             for key in ("act", "gact", "gW", "gWs", "gb"):
                 for a, b in zip(got[key], ref[key]):
-                    assert np.array_equal(a, b), (s is stream_s, rep, key)
+                    assert np.array_equal(a, b), (tag, rep, key)
 
 
 def test_streaming_partition_order_reuses_cached_blocks(monkeypatch):
