@@ -127,6 +127,7 @@ void compute_workspace(gnn_ctx* c)
     int64_t o = 0;
     auto take = [&](int64_t floats) { int64_t at = o; o += align_up(std::max<int64_t>(1, floats) * 4); return at; };
     w.z = take(max_np * din);
+    w.z2 = take(max_np * din);
     w.dy = take(max_np * dout);
     w.dz = take(max_np * din);
     w.dga = take(max_r * din);
@@ -195,7 +196,7 @@ void run_spmm_fwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, hipS
     const int32_t din = c->dims[(size_t)layer - 1];
     const SpmmItems items = plan_items(M.plan_fwd, c->D.fwd, p);
     const float* rscale = c->D.rscale ? c->D.rscale + r0 : nullptr;
-    void* Z = c->scratch + c->ws.z;
+    void* Z = c->scratch + c->z_off();
     float* segpart = (float*)(c->scratch + c->ws.segpart);
     const int b16 = c->bf16() ? 1 : 0;
     {
@@ -274,6 +275,21 @@ void compute_fwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, char*
     const int64_t np = M.off[(size_t)p + 1] - M.off[(size_t)p];
     const int32_t din = c->dims[(size_t)layer - 1], dout = c->dims[(size_t)layer];
     run_spmm_fwd(c, layer, p, in_own, s);
+    if (c->fwd_side) {
+        // gnn_epoch, resident: the contraction (and the dropout behind it) goes to the side stream
+        // once Z is complete, and the caller's stream moves on to the next partition's gather
+        hipEvent_t ready = c->side_events[c->side_events.size() - 3];
+        (void)hipEventRecord(ready, s);
+        (void)hipStreamWaitEvent(c->fwd_side, ready, 0);
+        s = c->fwd_side;
+    }
+    struct Release {        // the Z region is free again when everything launched below has run
+        gnn_ctx* c; hipStream_t s;
+        ~Release()
+        {
+            if (c->fwd_side) (void)hipEventRecord(c->side_events[c->side_events.size() - 2 + (size_t)c->z_slot], s);
+        }
+    } release{c, s};
     Timed t(c, s, GNN_K_GEMM_FWD);
     GemmEpilogue ep;
     ep.bias = c->has_bias ? (const float*)c->w[(size_t)3 * (layer - 1) + 2] : nullptr;
@@ -281,7 +297,7 @@ void compute_fwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, char*
     const bool sage = c->model == GNN_SAGE_MEAN;
     if (!c->bf16()) {
         GemmSeg seg[2];
-        seg[0].a = (const float*)(c->scratch + c->ws.z); seg[0].lda = din;
+        seg[0].a = (const float*)(c->scratch + c->z_off()); seg[0].lda = din;
         seg[0].b = (const float*)c->w[(size_t)3 * (layer - 1)]; seg[0].ldb = dout; seg[0].k = din;
         if (sage) {
             seg[1].a = (const float*)in_own; seg[1].lda = din;
@@ -290,7 +306,7 @@ void compute_fwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, char*
         launch_gemm_nn(seg, sage ? 2 : 1, (float*)out_own, dout, np, dout, ep, s);
     } else {
         GemmSegBf16 seg[2];
-        seg[0].a = c->scratch + c->ws.z; seg[0].lda = din;
+        seg[0].a = c->scratch + c->z_off(); seg[0].lda = din;
         seg[0].b = c->w[(size_t)3 * (layer - 1)]; seg[0].ldb = dout; seg[0].k = din;
         if (sage) {
             seg[1].a = in_own; seg[1].lda = din;
@@ -1146,7 +1162,7 @@ gnn_status gnn_epoch(gnn_ctx* c, void* stream, float* loss_out)
         if (st == GNN_OK && c->prof) collect_profile(c);
         return st;
     }
-    gnn_status st;
+    gnn_status st = GNN_OK;
     // Overlap (fp32 GCN / GraphSAGE): where an aggregate-first layer l sits below a transform-first
     // layer l + 1, the contractions of layer l + 1's own sweep (H_p = A_p^l W forward; grad W,
     // grad A_p^l backward) run on a side stream, partition by partition, beside layer l's gather /
@@ -1155,10 +1171,10 @@ gnn_status gnn_epoch(gnn_ctx* c, void* stream, float* loss_out)
     // region of their own; every dependency is an event, and each buffer sees its kernels in the
     // order of the one-stream schedule, so the results are the same bits.  GNNMI_OVERLAP=0: off.
     const char* overlap_env = std::getenv("GNNMI_OVERLAP");          // read per epoch: tests flip it
-    bool overlap = !(overlap_env && overlap_env[0] == '0') && !c->bf16() && c->model != GNN_GAT && L >= 2;
+    bool overlap = !(overlap_env && overlap_env[0] == '0') && !c->bf16() && c->model != GNN_GAT;
     if (overlap) {
-        bool any = false;
-        for (int32_t l = 1; l < L; ++l) any = any || (!c->transform_first(l) && c->transform_first(l + 1));
+        bool any = false;                 // an aggregate-first layer: its forward contraction moves too
+        for (int32_t l = 1; l <= L; ++l) any = any || !c->transform_first(l);
         overlap = any;
     }
     if (overlap && !c->side) {
@@ -1169,7 +1185,7 @@ gnn_status gnn_epoch(gnn_ctx* c, void* stream, float* loss_out)
         }
     }
     if (overlap)
-        while (c->side_events.size() < (size_t)k + 2) {
+        while (c->side_events.size() < (size_t)k + 5) {   // k steps, two fences, Z ready, two Z regions free
             hipEvent_t e;
             if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) {
                 (void)hipGetLastError();
@@ -1200,18 +1216,28 @@ gnn_status gnn_epoch(gnn_ctx* c, void* stream, float* loss_out)
         if (c->transform_first(l) && !paired(l - 1))
             for (int32_t t = 0; t < k; ++t)
                 if ((st = gnn_layer_transform_fwd(c, l, c->M.sched[(size_t)t], stream)) != GNN_OK) return st;
+        // an aggregate-first layer: Z_p is aggregated on the caller's stream into one of two
+        // regions, its contraction (and layer l + 1's, when that layer transforms first) follows
+        // on the side stream while the caller's stream gathers and aggregates the next partition
+        const bool side_fwd = overlap && !c->transform_first(l);
         for (int32_t t = 0; t < k; ++t) {
             const int32_t p = c->M.sched[(size_t)t];
-            if ((st = gnn_gather_boundary(c, l, p, stream)) != GNN_OK) return st;
-            if ((st = gnn_layer_fwd(c, l, p, stream)) != GNN_OK) return st;
-            if (paired(l)) {
-                // A_p^l is complete on the caller's stream: layer l + 1 transforms it on the side
-                if ((st = hip_ok(hipEventRecord(step_event[t], s), "hipEventRecord")) != GNN_OK) return st;
-                if ((st = hip_ok(hipStreamWaitEvent(c->side, step_event[t], 0), "hipStreamWaitEvent")) != GNN_OK) return st;
-                if ((st = gnn_layer_transform_fwd(c, l + 1, p, (void*)c->side)) != GNN_OK) return st;
+            if (side_fwd) {
+                c->z_slot = t & 1;
+                // the contraction that read this region two steps ago
+                const hipEvent_t z_free = c->side_events[c->side_events.size() - 2 + (size_t)c->z_slot];
+                if ((st = hip_ok(hipStreamWaitEvent(s, z_free, 0), "hipStreamWaitEvent")) != GNN_OK) break;
+                c->fwd_side = c->side;
             }
+            if ((st = gnn_gather_boundary(c, l, p, stream)) != GNN_OK) break;
+            if ((st = gnn_layer_fwd(c, l, p, stream)) != GNN_OK) break;
+            // A_p^l is complete on the side stream, in order: layer l + 1 transforms it there
+            if (paired(l) && (st = gnn_layer_transform_fwd(c, l + 1, p, (void*)c->side)) != GNN_OK) break;
         }
-        if (paired(l)) {
+        c->fwd_side = nullptr;
+        c->z_slot = 0;
+        if (st != GNN_OK) return st;
+        if (side_fwd) {
             if ((st = hip_ok(hipEventRecord(fence_side, c->side), "hipEventRecord")) != GNN_OK) return st;
             if ((st = hip_ok(hipStreamWaitEvent(s, fence_side, 0), "hipStreamWaitEvent")) != GNN_OK) return st;
         }

@@ -48,6 +48,9 @@ struct Workspace {  // byte offsets into `scratch`
     int64_t dyall = -1;
     // second split-K partial region, for contractions that gnn_epoch runs on its side stream
     int64_t partial2 = 0;
+    // second Z region: the resident epoch alternates between the two while the contraction of
+    // the previous partition still reads the other one on the side stream
+    int64_t z2 = 0;
     // graph attention: per-vertex scores and their gradients, staged boundary scores, per-entry
     // attention weights, edge-wise products, attention weights in transposed order
     int64_t ssrc = 0, sdst = 0, gssrc = 0, gsdst = 0, bs = 0, att = 0, dal = 0, twatt = 0;
@@ -122,6 +125,9 @@ struct gnn_ctx {
     hipStream_t side = nullptr;
     std::vector<hipEvent_t> side_events;   // per schedule step, plus two fences
     bool on_side = false;                  // calls made for the side stream take the second partial region
+    hipStream_t fwd_side = nullptr;        // set by gnn_epoch: compute_fwd puts its contraction there
+    int z_slot = 0;                        // which Z region compute_fwd uses (0 outside gnn_epoch's forward)
+    int64_t z_off() const { return z_slot ? ws.z2 : ws.z; }
 
     gnn_status fail(gnn_status st, const std::string& msg) const
     {
