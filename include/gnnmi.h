@@ -251,8 +251,8 @@ gnn_status gnn_layer_bwd(gnn_ctx *ctx, int32_t layer, int32_t p, void *stream);
 
 /* One epoch: forward over all layers and partitions, loss, backward; grad_w is overwritten.
  * Synchronises `stream` before writing *loss_out (host).  Resident schedule, fp32 GCN /
- * GraphSAGE: the forward contraction of an aggregate-first layer, and where such a layer lies
- * below a transform-first one the upper layer's contractions of its own sweep, run on a stream
+ * GraphSAGE: the forward contraction of an aggregate-first layer below another one, and where
+ * such a layer lies below a transform-first one that layer's contractions of its own sweep, run on a stream
  * the context owns, beside the gathers and aggregations of the other partitions, ordered
  * against `stream` by events only (so `stream` may be the null stream or
  * any other); results are the one-stream schedule's bits.  Everything the epoch launched has

@@ -1217,9 +1217,11 @@ gnn_status gnn_epoch(gnn_ctx* c, void* stream, float* loss_out)
             for (int32_t t = 0; t < k; ++t)
                 if ((st = gnn_layer_transform_fwd(c, l, c->M.sched[(size_t)t], stream)) != GNN_OK) return st;
         // an aggregate-first layer: Z_p is aggregated on the caller's stream into one of two
-        // regions, its contraction (and layer l + 1's, when that layer transforms first) follows
-        // on the side stream while the caller's stream gathers and aggregates the next partition
-        const bool side_fwd = overlap && !c->transform_first(l);
+        // regions and its contraction follows on the side stream while the caller's stream
+        // gathers and aggregates the next partition
+        // (not when layer l + 1 keeps the side stream busy already: measured neutral in wall time
+        // there, and it only stretches the aggregation kernels further)
+        const bool side_fwd = overlap && !c->transform_first(l) && !paired(l);
         for (int32_t t = 0; t < k; ++t) {
             const int32_t p = c->M.sched[(size_t)t];
             if (side_fwd) {
@@ -1231,13 +1233,17 @@ gnn_status gnn_epoch(gnn_ctx* c, void* stream, float* loss_out)
             }
             if ((st = gnn_gather_boundary(c, l, p, stream)) != GNN_OK) break;
             if ((st = gnn_layer_fwd(c, l, p, stream)) != GNN_OK) break;
-            // A_p^l is complete on the side stream, in order: layer l + 1 transforms it there
-            if (paired(l) && (st = gnn_layer_transform_fwd(c, l + 1, p, (void*)c->side)) != GNN_OK) break;
+            if (paired(l)) {
+                // A_p^l is complete on the caller's stream: layer l + 1 transforms it on the side
+                if ((st = hip_ok(hipEventRecord(step_event[t], s), "hipEventRecord")) != GNN_OK) break;
+                if ((st = hip_ok(hipStreamWaitEvent(c->side, step_event[t], 0), "hipStreamWaitEvent")) != GNN_OK) break;
+                if ((st = gnn_layer_transform_fwd(c, l + 1, p, (void*)c->side)) != GNN_OK) break;
+            }
         }
         c->fwd_side = nullptr;
         c->z_slot = 0;
         if (st != GNN_OK) return st;
-        if (side_fwd) {
+        if (side_fwd || paired(l)) {
             if ((st = hip_ok(hipEventRecord(fence_side, c->side), "hipEventRecord")) != GNN_OK) return st;
             if ((st = hip_ok(hipStreamWaitEvent(s, fence_side, 0), "hipStreamWaitEvent")) != GNN_OK) return st;
         }

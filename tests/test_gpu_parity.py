@@ -566,16 +566,20 @@ def test_transform_first_layers_match_oracle(name, dims):
     assert not any(s0.ctx.layer_is_transform_first(l) for l in range(1, L + 1))
 
 
-@pytest.mark.parametrize("name,dims", [("tiny", None),                      # gcn, output layer paired
-                                       ("mini_sage", (24, 30, 10, 7)),      # hidden pair, padded rows
-                                       ("mini_sage", (24, 32, 8)),          # sage output layer without padding
-                                       ("mini_sage", (24, 32, 7)),          # sage output layer, padded: forward pair only
-                                       ("mini_gcn_directed", (20, 24, 9, 9, 5))])
-def test_side_stream_overlap_gives_the_one_stream_bits(monkeypatch, name, dims):
+@pytest.mark.parametrize("name,dims,order", [
+    ("tiny", None, "auto"),                              # gcn, output layer paired
+    ("mini_sage", (24, 30, 10, 7), "auto"),              # hidden pair, padded rows
+    ("mini_sage", (24, 32, 8), "auto"),                  # sage output layer without padding
+    ("mini_sage", (24, 32, 7), "auto"),                  # sage output layer, padded: forward pair only
+    ("mini_gcn_directed", (20, 24, 9, 9, 5), "auto"),
+    ("mini_sage", (24, 32, 16, 7), "aggregate"),         # every layer aggregates first: forward contractions
+    ("mini_gcn_directed", (20, 9, 12, 5), "aggregate")])
+def test_side_stream_overlap_gives_the_one_stream_bits(monkeypatch, name, dims, order):
     """gnn_epoch runs a transform-first layer's contractions on a side stream beside the
-    aggregate-first layer below it; with GNNMI_OVERLAP=0 everything runs on the caller's stream.
-    Same bits, epoch after epoch, also with dropout and optimizer steps in between."""
-    say("case overlap %s %s" % (name, dims))
+    aggregate-first layer below it, and the forward contraction of an aggregate-first layer below
+    another one; with GNNMI_OVERLAP=0 everything runs on the caller's stream.  Same bits, epoch
+    after epoch, also with dropout and optimizer steps in between."""
+    say("case overlap %s %s %s" % (name, dims, order))
     from paper_2605_11517_amd import Session
     over = {} if dims is None else {"dims": dims}
     cfg, rowptr, colidx = make_config(name, **over)
@@ -585,9 +589,12 @@ def test_side_stream_overlap_gives_the_one_stream_bits(monkeypatch, name, dims):
     out = {}
     for flag in ("0", "1"):
         monkeypatch.setenv("GNNMI_OVERLAP", flag)
-        s = Session(model, dims, rowptr, colidx, k, cfg["part"], cfg["seed"], X, w, y, m, layer_order="auto")
+        s = Session(model, dims, rowptr, colidx, k, cfg["part"], cfg["seed"], X, w, y, m, layer_order=order)
         xf = [s.ctx.layer_is_transform_first(l) for l in range(1, L + 1)]
-        assert any((not a) and b for a, b in zip(xf, xf[1:])), xf        # there is a pair to overlap
+        if order == "auto":
+            assert any((not a) and b for a, b in zip(xf, xf[1:])), xf    # there is a pair to overlap
+        else:
+            assert not any(xf)
         losses = [s.epoch(), s.epoch()]
         r = s.results()
         losses += s.train(3, optimizer="adam", lr=0.01, dropout=0.3, seed=5)
