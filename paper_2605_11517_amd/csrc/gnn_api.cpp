@@ -605,17 +605,7 @@ static void xf_aggregate_bwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s
         dYp = pad;
     }
     if (c->model == GNN_SAGE_MEAN) {
-        if (keep && c->bwd_side) {
-            // gnn_epoch, resident: the kept dY rows outlive this call, so grad W_s = A_p^{l-1 T} dY_p
-            // can run on the side stream (with its own split-K region) beside the transposed
-            // aggregation below; nothing on the caller's stream reads that gradient
-            hipEvent_t ready = c->side_events[c->side_events.size() - 3];
-            (void)hipEventRecord(ready, s);
-            (void)hipStreamWaitEvent(c->bwd_side, ready, 0);
-            Timed t(c, c->bwd_side, GNN_K_GEMM_DW);
-            launch_gemm_tn(in_own, din, dYp, dp, c->gw[(size_t)3 * (layer - 1) + 1], dout, din, dout, np,
-                           (float*)(c->scratch + c->ws.partial2), c->bwd_side);
-        } else {
+        {
             Timed t(c, s, GNN_K_GEMM_DW);
             launch_gemm_tn(in_own, din, dYp, dp, c->gw[(size_t)3 * (layer - 1) + 1], dout, din, dout, np,
                            (float*)(c->scratch + c->ws.partial), s);
@@ -1267,24 +1257,15 @@ gnn_status gnn_epoch(gnn_ctx* c, void* stream, float* loss_out)
             // attention needs H and the scores of this layer again: recompute them
             for (int32_t t = 0; t < k; ++t)
                 if ((st = gnn_layer_transform_fwd(c, l, c->M.sched[(size_t)t], stream)) != GNN_OK) return st;
-        if (overlap && xf) c->bwd_side = c->side;
         for (int32_t t = 0; t < k; ++t) {
             const int32_t p = c->M.sched[(size_t)t];
             if (wait_steps &&
                 (st = hip_ok(hipStreamWaitEvent(s, step_event[t], 0), "hipStreamWaitEvent")) != GNN_OK)
-                break;
-            if (regather && (st = gnn_gather_boundary(c, l, p, stream)) != GNN_OK) break;
-            if ((st = gnn_layer_bwd(c, l, p, stream)) != GNN_OK) break;
+                return st;
+            if (regather && (st = gnn_gather_boundary(c, l, p, stream)) != GNN_OK) return st;
+            if ((st = gnn_layer_bwd(c, l, p, stream)) != GNN_OK) return st;
         }
-        const bool used_side = c->bwd_side != nullptr;
-        c->bwd_side = nullptr;
-        if (st != GNN_OK) return st;
         wait_steps = false;
-        if (used_side && !paired_bwd(l - 1)) {
-            // whatever the first sweep put on the side stream is ordered before the rest of the epoch
-            if ((st = hip_ok(hipEventRecord(fence_side, c->side), "hipEventRecord")) != GNN_OK) return st;
-            if ((st = hip_ok(hipStreamWaitEvent(s, fence_side, 0), "hipStreamWaitEvent")) != GNN_OK) return st;
-        }
         if (xf && paired_bwd(l - 1)) {
             // grad H of this layer is complete on the caller's stream: its contractions go to the
             // side stream, and partition p of layer l - 1 starts when grad A_p^{l-1} is there

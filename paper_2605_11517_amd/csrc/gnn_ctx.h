@@ -126,7 +126,6 @@ struct gnn_ctx {
     std::vector<hipEvent_t> side_events;   // per schedule step, plus two fences
     bool on_side = false;                  // calls made for the side stream take the second partial region
     hipStream_t fwd_side = nullptr;        // set by gnn_epoch: compute_fwd puts its contraction there
-    hipStream_t bwd_side = nullptr;        // set by gnn_epoch: a hidden GraphSAGE layer's self-weight gradient goes there
     int z_slot = 0;                        // which Z region compute_fwd uses (0 outside gnn_epoch's forward)
     int64_t z_off() const { return z_slot ? ws.z2 : ws.z; }
 
