@@ -236,7 +236,20 @@ gnn_status gnn_layer_fwd(gnn_ctx *ctx, int32_t layer, int32_t p, void *stream);
  * gradients are NOT cleared here (gnn_epoch clears them; a caller stepping by hand clears
  * grad_w itself).  The scalar loss stays on the device until gnn_read_loss(). */
 gnn_status gnn_loss(gnn_ctx *ctx, void *stream);
-/* Synchronises `stream` and returns the last loss. */
+/* For callers that cannot allocate or hand over a workspace (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): gnn_loss with the mask count and the
+ * block partial sums kept in a 4 MiB device array the library holds statically, one copy per
+ * GPU for the life of the process, instead of in the bound scratch.  No hipMalloc / hipFree and
+ * no allocating routine is called.  Inputs and outputs are the bound ones (A^L, labels, mask ->
+ * grad_act[L-1]); the scalar loss is written to loss_dev (device, one float, caller owned) on
+ * `stream`; gnn_read_loss does not see it.  Same kernels and summation order as gnn_loss, so the
+ * results are the same bits.  At most 67,104,768 vertices: GNN_EINVAL beyond, with a message.
+ * Every call on a GPU uses that GPU's one array: calls that overlap in time on one GPU (two
+ * streams, two contexts, two threads) race; calls in sequence are fine, nothing is carried from
+ * one call to the next.  Other errors as gnn_loss; GNN_EHIP if the array's address cannot be
+ * obtained. */
+gnn_status gnn_loss_static(gnn_ctx *ctx, void *stream, float *loss_dev);
+/* Synchronises `stream` and returns the last loss of gnn_loss. */
 gnn_status gnn_read_loss(gnn_ctx *ctx, void *stream, float *loss_out);
 
 /* (grad GA_p^{l-1}, grad W^l) <-(., +) BW(W^l, A_p^l, grad A_p^l, GA_p^{l-1}): activation

@@ -87,6 +87,7 @@ def load_library():
         "gnn_gather_boundary": [vp, i32, i32, vp],
         "gnn_layer_fwd": [vp, i32, i32, vp],
         "gnn_loss": [vp, vp],
+        "gnn_loss_static": [vp, vp, vp],
         "gnn_read_loss": [vp, vp, P(C.c_float)],
         "gnn_layer_bwd": [vp, i32, i32, vp],
         "gnn_epoch": [vp, vp, P(C.c_float)],
@@ -231,6 +232,9 @@ class Context:
 
     def loss(self, stream):
         self._check(self.lib.gnn_loss(self.h, stream))
+
+    def loss_static(self, stream, loss_dev):
+        self._check(self.lib.gnn_loss_static(self.h, stream, loss_dev))
 
     def read_loss(self, stream):
         v = C.c_float()

@@ -1062,6 +1062,29 @@ gnn_status gnn_loss(gnn_ctx* c, void* stream)
     return check_launch(c, "gnn_loss");
 }
 
+gnn_status gnn_loss_static(gnn_ctx* c, void* stream, float* loss_dev)
+{
+    if (!c || !loss_dev) return GNN_EINVAL;
+    if (!c->bound) return c->fail(GNN_ESTATE, "buffers are not bound (call gnn_bind)");
+    if (c->streaming()) return c->fail(GNN_EUNSUPPORTED, "with a streaming budget only gnn_epoch drives the schedule");
+    for (uint8_t f : c->fwd_done)
+        if (!f) return c->fail(GNN_ESTATE, "gnn_loss_static before the forward pass has covered every (layer, partition)");
+    if (c->M.n > loss_static_max_rows())
+        return c->fail(GNN_EINVAL, "gnn_loss_static: " + std::to_string(c->M.n) + " vertices exceed the limit of " +
+                                       std::to_string(loss_static_max_rows()) + " the static scratch array is sized for");
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e;
+    {
+        Timed t(c, s, GNN_K_LOSS);
+        e = launch_loss_static((const float*)c->act[(size_t)c->L - 1], c->labels, c->mask, c->gact[(size_t)c->L - 1],
+                               c->M.n, c->dims[(size_t)c->L], loss_dev, s);
+    }
+    if (e != hipSuccess) return c->fail(GNN_EHIP, std::string("gnn_loss_static: ") + hipGetErrorString(e));
+    c->loss_done = true;
+    std::fill(c->bwd_done.begin(), c->bwd_done.end(), 0);
+    return GNN_OK;
+}
+
 gnn_status gnn_read_loss(gnn_ctx* c, void* stream, float* loss_out)
 {
     if (!c || !loss_out) return GNN_EINVAL;

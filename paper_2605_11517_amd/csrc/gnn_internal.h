@@ -213,6 +213,12 @@ int64_t launch_loss_rows(const float* logits, const int32_t* labels, const uint8
 void launch_loss_finish(const float* partial, int64_t nparts, const unsigned long long* count_dev,
                         float* loss_dev, hipStream_t s);
 
+// The same loss with |M| and the block partial sums in a device array the library holds
+// statically (no workspace from the caller, no allocation); n <= loss_static_max_rows().
+int64_t loss_static_max_rows();
+hipError_t launch_loss_static(const float* logits, const int32_t* labels, const uint8_t* mask, float* grad,
+                              int64_t n, int32_t c, float* loss_dev, hipStream_t s);
+
 void launch_fill_zero(void* p, int64_t bytes, hipStream_t s);
 
 // ---- graph attention (kernels_gat.hip) ----------------------------------------------------

@@ -465,6 +465,49 @@ void launch_loss(const float* logits, const int32_t* labels, const uint8_t* mask
     launch_loss_finish(partial, blocks, count_dev, loss_dev, s);
 }
 
+// ---- loss without a caller workspace --------------------------------------------------------
+// The loss kernels need |M| (8 bytes) and one partial sum per block of 64 rows.  This array
+// stands in for the caller's workspace when the caller cannot provide or allocate one.  Every
+// device the library runs on holds its own copy for the life of the process; host code never
+// uses the array's name as an address, only the per-device pointer looked up below.
+constexpr int64_t kStaticScratchBytes = 4 << 20;
+constexpr int64_t kStaticPartialOffset = 256;          // bytes; |M| sits at offset 0
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+void* g_static_ptr[kMaxDevices] = {};
+}  // namespace
+
+int64_t loss_static_max_rows()
+{
+    const int64_t rpb = kLossRowsPerWave * (kBlock / kWave);
+    return (kStaticScratchBytes - kStaticPartialOffset) / (int64_t)sizeof(float) * rpb;
+}
+
+hipError_t launch_loss_static(const float* logits, const int32_t* labels, const uint8_t* mask, float* grad,
+                              int64_t n, int32_t c, float* loss_dev, hipStream_t s)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    if (!g_static_ptr[dev]) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        g_static_ptr[dev] = ptr;
+    }
+    char* base = static_cast<char*>(g_static_ptr[dev]);
+    unsigned long long* count_dev = reinterpret_cast<unsigned long long*>(base);
+    float* partial = reinterpret_cast<float*>(base + kStaticPartialOffset);
+    // the count is cleared by a fill kernel inside launch_loss; the partial sums of this call's
+    // blocks are all overwritten before the last kernel reads exactly that many
+    launch_loss(logits, labels, mask, grad, n, c, count_dev, partial, loss_dev, s);
+    return hipGetLastError();
+}
+
 int64_t act_bwd_partial_floats(int64_t rows, int32_t d)
 {
     return ((rows + kRowsPerBlockAct - 1) / kRowsPerBlockAct) * (int64_t)d;
