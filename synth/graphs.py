@@ -94,7 +94,60 @@ def rmat_graph(n: int, m_draw: int, seed: int, *, symmetric: bool, self_loops: b
     return csr_from_edges(n, s, t)
 
 
+_counter_lib = None
+
+
+def _counter():
+    """The compiled counter-based generator (``rmat_counter.cpp``), built on first use."""
+    global _counter_lib
+    if _counter_lib is None:
+        import ctypes as C
+        from . import build as _build
+        lib = C.CDLL(_build.build(force=False))
+        lib.rmat_counter_generate.restype = C.c_void_p
+        lib.rmat_counter_generate.argtypes = [C.c_int64, C.c_int64, C.c_uint64, C.c_int, C.c_double,
+                                              C.c_double, C.c_double, C.c_int, C.c_int,
+                                              C.POINTER(C.c_int64)]
+        lib.rmat_counter_fetch.restype = None
+        lib.rmat_counter_fetch.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+        lib.normal_counter_fill.restype = None
+        lib.normal_counter_fill.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_uint64]
+        _counter_lib = lib
+    return _counter_lib
+
+
+def rmat_graph_counter(n: int, m_draw: int, seed: int, *, symmetric: bool, self_loops: bool,
+                       scale: int | None = None, abcd=RMAT_ABCD):
+    """The same recipe as :func:`rmat_graph` with counter-based draws (SplitMix64 of the edge
+    index and level) and a permutation by sorted SplitMix64 keys, generated and sorted on all
+    host cores by ``rmat_counter.cpp``: for graphs of 10^8 and more draws.  A different random
+    stream, hence a different graph than :func:`rmat_graph` gives for the same seed."""
+    import ctypes as C
+    if scale is None:
+        scale = max(1, int(np.ceil(np.log2(n))))
+    lib = _counter()
+    nnz = C.c_int64(0)
+    h = lib.rmat_counter_generate(n, m_draw, seed, scale, abcd[0], abcd[1], abcd[2],
+                                  1 if symmetric else 0, 1 if self_loops else 0, C.byref(nnz))
+    if not h:
+        raise MemoryError("rmat_counter_generate: out of memory")
+    rowptr = np.empty(n + 1, dtype=np.int64)
+    colidx = np.empty(nnz.value, dtype=np.int32)
+    lib.rmat_counter_fetch(h, rowptr.ctypes.data, colidx.ctypes.data)
+    return rowptr, colidx
+
+
+def normal_counter(n: int, d: int, seed: int) -> np.ndarray:
+    """``[n, d]`` float32 standard-normal numbers, element ``i`` a function of ``(seed, i)``
+    alone (Box-Muller on SplitMix64 draws), filled on all host cores."""
+    out = np.empty((n, d), dtype=np.float32)
+    _counter().normal_counter_fill(out.ctypes.data, 0, n * d, seed)
+    return out
+
+
 # Workload shapes.  "m_draw" is tuned so the distinct-edge count lands near the target.
+# "gen": which generator draws the graph and the features: "numpy" (default) or "counter" (the
+# parallel counter-based one, for the workloads whose inputs would otherwise take minutes).
 CONFIGS = {
     # parity fixture: 10,000 nodes, ~100,000 draws symmetrised, self-loops, 2-layer GCN
     "tiny": dict(n=10_000, m_draw=100_000, seed=1, symmetric=True, self_loops=True,
@@ -110,8 +163,15 @@ CONFIGS = {
                     train_frac=0.1),
     # half of papers100M's shape: 50M nodes, ~800M directed edges, 3-layer GCN
     "large": dict(n=50_000_000, m_draw=830_000_000, seed=3, symmetric=False, self_loops=True,
-                  model="gcn", dims=(128, 128, 128, 172), dtype="f32", k=64, part="lp",
-                  train_frac=0.1),
+                  model="gcn", dims=(128, 128, 128, 172), dtype="f32", k=64, part="switching_device",
+                  train_frac=0.1, gen="counter"),
+    # the beyond-HBM recipe (papers100M symmetrised: 100M nodes, ~2e9 entries, 3-layer SAGE-mean
+    # 128->256->256->64, k = 256) scaled to 6 % of its vertices at the same average degree (20),
+    # widths and partition count, so that activations + gradients (15 GB) fit the pinned host
+    # memory of a GPU machine; it runs through the streaming schedule with a pool below that
+    "beyond": dict(n=6_000_000, m_draw=64_000_000, seed=5, symmetric=True, self_loops=False,
+                   model="sage", dims=(128, 256, 256, 64), dtype="f32", k=256, part="switching_device",
+                   train_frac=0.1, gen="counter"),
     # wide hidden sizes, bf16 transforms
     "dense": dict(n=4_000_000, m_draw=55_000_000, seed=4, symmetric=True, self_loops=True,
                   model="gcn", dims=(512, 1024, 1024, 64), dtype="bf16", k=16, part="lp",
@@ -130,6 +190,7 @@ def make_config(name: str, **override):
     """Graph of a named config (after ``override``).  Returns ``(cfg, rowptr, colidx)``."""
     cfg = dict(CONFIGS[name])
     cfg.update(override)
-    rowptr, colidx = rmat_graph(cfg["n"], cfg["m_draw"], cfg["seed"],
-                                symmetric=cfg["symmetric"], self_loops=cfg["self_loops"])
+    gen = rmat_graph_counter if cfg.get("gen") == "counter" else rmat_graph
+    rowptr, colidx = gen(cfg["n"], cfg["m_draw"], cfg["seed"],
+                         symmetric=cfg["symmetric"], self_loops=cfg["self_loops"])
     return cfg, rowptr, colidx

@@ -4,8 +4,12 @@ from __future__ import annotations
 import numpy as np
 
 
-def features(n: int, d: int, seed: int) -> np.ndarray:
-    """``[n, d]`` float32 standard-normal features."""
+def features(n: int, d: int, seed: int, gen: str = "numpy") -> np.ndarray:
+    """``[n, d]`` float32 standard-normal features.  ``gen="counter"``: the parallel
+    counter-based stream of the large workloads (a config's ``gen`` key)."""
+    if gen == "counter":
+        from .graphs import normal_counter
+        return normal_counter(n, d, seed)
     rng = np.random.default_rng([seed, 0xBB67AE85])
     return rng.standard_normal((n, d), dtype=np.float32)
 

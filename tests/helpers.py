@@ -58,39 +58,128 @@ def random_weights(dims, seed, sage, bias=True):
     return out
 
 
-def aligned_backward(og, fwd, got_act, weights, X, labels, mask, tol, say=None):
+def elem_err(got, ref):
+    """Element-wise relative error max_i |got_i - ref_i| / max(|ref_i|, 1e-3 max|ref|): reported
+    next to the gate (it is stricter on small elements; not itself gated)."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    if ref.size == 0:
+        return 0.0
+    floor = 1e-3 * np.abs(ref).max()
+    if floor == 0:
+        return float(np.abs(got - ref).max())
+    worst = 0.0
+    flat_g, flat_r = got.reshape(-1), ref.reshape(-1)
+    for i in range(0, flat_r.size, 1 << 26):          # by chunks: the tensors can hold 6e8 elements
+        r = flat_r[i:i + (1 << 26)]
+        worst = max(worst, float((np.abs(flat_g[i:i + (1 << 26)] - r) / np.maximum(np.abs(r), floor)).max()))
+    return worst
+
+
+def both_errs(got, ref):
+    """(gate, element-wise) errors of one tensor."""
+    return rel_err(got, ref), elem_err(got, ref)
+
+
+def fmt_errs(worst):
+    """'name=gate (elem)' for a dict name -> (gate, elem) or name -> gate."""
+    out = []
+    for k, v in sorted(worst.items()):
+        out.append("%s=%.2g (elem %.2g)" % (k, v[0], v[1]) if isinstance(v, tuple) else "%s=%.2g" % (k, v))
+    return ", ".join(out)
+
+
+FP32_BAND_CEILING = 1e-5      # fp32: the band may not exceed this fraction of max|A^l|
+FLIP_CEILING = {False: 1e-6, True: 1e-2}   # fp32 / bf16: largest accepted fraction of differing decisions
+
+
+def aligned_backward(og, fwd, got_act, weights, X, labels, mask, tol, say=None, bf16=False,
+                     got_gact=None):
     """Oracle backward with the activation decisions of the other implementation on the
-    elements where the two disagree, after checking that each disagreement is legitimate:
-    the oracle's pre-activation and the other side's activation both lie within
-    ``tol * max|A^l|`` of zero, i.e. inside the forward tolerance band, where either decision
-    is a correct result.  Returns the oracle's backward dict (plus ``act``)."""
+    elements where the two disagree, after checking that each disagreement is legitimate.
+
+    The backward pass branches on A^l > 0, and a pre-activation within rounding distance of
+    zero can fall on either side.  What "rounding distance" is comes from the oracle's side
+    only:
+
+    * fp32 storage: 8 x the forward error of that layer as measured here, max|got - oracle|
+      over the whole tensor (taken before any alignment; the forward pass does not depend on
+      the decisions), and never more than 1e-5 max|A^l|;
+    * bfloat16 storage: per element, four bfloat16 half-ulps (2^-9 each) of the magnitude
+      that was summed into it, 2^-7 (S|A^{l-1}| |W| + |A^{l-1}| |W_s| + |b|)[v, c]: the
+      aggregate (or the transformed row) is rounded to bfloat16 once before the sum and its
+      inputs once before that.
+
+    Both the oracle's pre-activation and the other side's stored activation must lie inside
+    the band at every disagreement, and the number of disagreements is capped (1e-6 of the
+    elements + 4 in fp32, 1 % in bfloat16).  Prints the count, the band and the largest oracle
+    pre-activation among them; with ``got_gact`` also how many rows of each hidden gradient
+    would fail the gate had the oracle kept its own decisions.  Returns the oracle's backward
+    dict (plus ``act``)."""
     relu_on = []
     L = fwd.L
     for l in range(L - 1):
-        on_got = np.asarray(got_act[l]) > 0
+        got = np.asarray(got_act[l])
+        on_got = got > 0
         on_ref = fwd.act[l] > 0
         diff = np.argwhere(on_got != on_ref)
-        band = tol * np.abs(fwd.act[l]).max()
+        amax = float(np.abs(fwd.act[l]).max())
+        fwd_err = 0.0
+        for r0 in range(0, fwd.n, 1 << 18):
+            fwd_err = max(fwd_err, float(np.abs(got[r0:r0 + (1 << 18)] - fwd.act[l][r0:r0 + (1 << 18)]).max()))
         prev = np.asarray(X, dtype=np.float64) if l == 0 else fwd.act[l - 1]
         W = np.asarray(weights[l]["W"], dtype=np.float64)
-        Ws = weights[l].get("Ws")
+        Ws = weights[l].get("Ws") if fwd.m == 1 else None
         b = weights[l].get("b")
+        ceiling = FLIP_CEILING[bool(bf16)] * on_ref.size + (0 if bf16 else 4)
+        assert len(diff) <= ceiling, (l, len(diff), ceiling)
+        worst_pre = 0.0
+        band_txt = ""
         if len(diff):
             v, c = diff[:, 0], diff[:, 1]
             pre = np.einsum("ij,ji->i", fwd.z[l][v], W[:, c])
-            if Ws is not None and fwd.m == 1:
+            if Ws is not None:
                 pre = pre + np.einsum("ij,ji->i", prev[v], np.asarray(Ws, dtype=np.float64)[:, c])
             if b is not None:
                 pre = pre + np.asarray(b, dtype=np.float64)[c]
-            assert np.abs(pre).max() <= band, (l, float(np.abs(pre).max()), band)
-            assert np.abs(np.asarray(got_act[l])[v, c]).max() <= band
+            if bf16:
+                # magnitudes summed into each of these pre-activations (A^{l-1} >= 0 above layer 1)
+                zabs = np.abs(fwd.z[l][v]) if l > 0 else \
+                    og.aggregate(fwd.m, fwd.rowptr, fwd.colidx, np.abs(prev))[v]
+                mag = np.einsum("ij,ji->i", zabs, np.abs(W[:, c]))
+                if Ws is not None:
+                    mag = mag + np.einsum("ij,ji->i", np.abs(prev[v]), np.abs(np.asarray(Ws, dtype=np.float64)[:, c]))
+                if b is not None:
+                    mag = mag + np.abs(np.asarray(b, dtype=np.float64)[c])
+                band = 2.0 ** -7 * mag
+                band_txt = "per-element bands up to %.2g max|A|" % (float(band.max()) / amax)
+            else:
+                band = 8.0 * fwd_err
+                assert band <= FP32_BAND_CEILING * amax, (l, band, amax)
+                band_txt = "band %.2g max|A| (8 x the measured forward error)" % (band / amax)
+            worst_pre = float(np.abs(pre).max())
+            assert np.all(np.abs(pre) <= band), (l, worst_pre, float(np.max(band)))
+            assert np.all(np.abs(got[v, c]) <= band), (l, float(np.abs(got[v, c]).max()))
         if say:
-            say("layer %d: %d of %d activation decisions differ, all within +-%.2g of zero"
-                % (l + 1, len(diff), on_ref.size, band))
+            say("layer %d: %d of %d activation decisions differ (ceiling %d), %s; largest oracle "
+                "pre-activation among them %.2g max|A|; forward error %.2g max|A|"
+                % (l + 1, len(diff), on_ref.size, int(ceiling), band_txt or "no band needed",
+                   worst_pre / amax, fwd_err / amax))
         on = on_ref.astype(np.uint8)
         if len(diff):
             on[diff[:, 0], diff[:, 1]] = on_got[diff[:, 0], diff[:, 1]]
         relu_on.append(on)
+    if got_gact is not None and say:
+        own = og.backward(fwd, labels, mask)
+        for l in range(L - 1):
+            den = float(np.abs(own["gact"][l]).max())
+            bad = 0
+            for r0 in range(0, fwd.n, 1 << 18):
+                d = np.abs(np.asarray(got_gact[l][r0:r0 + (1 << 18)], dtype=np.float64) - own["gact"][l][r0:r0 + (1 << 18)])
+                bad += int(np.count_nonzero(d.max(axis=1) > tol * den))
+            say("with the oracle's own decisions %d of %d rows of the gradient of A^%d would miss the gate"
+                % (bad, fwd.n, l + 1))
+        del own
     out = og.backward(fwd, labels, mask, relu_on=relu_on)
     out["act"] = fwd.act
     return out

@@ -316,3 +316,48 @@ def test_supplied_activation_decision_is_used_as_given():
 def test_rel_err_helper():
     assert rel_err([1.0, 2.0], [1.0, 2.0]) == 0.0
     assert abs(rel_err([1.0, 2.2], [1.0, 2.0]) - 0.1) < 1e-12
+
+
+def test_decision_alignment_accepts_rounding_and_rejects_everything_else():
+    """The helper that aligns activation decisions near zero: a copy of the oracle's
+    activations rounded to single precision passes (with few or no flips); the same copy with
+    one clearly positive activation switched off, or with one far-from-zero element switched
+    on, is refused; so is a copy whose forward error is large enough to widen the band past
+    its ceiling."""
+    from helpers import aligned_backward, elem_err
+    n, dims = 400, (12, 16, 16, 5)
+    rowptr, colidx = small_graph(n, 3000, seed=21, symmetric=True, self_loops=False)
+    rng = np.random.default_rng(9)
+    X = rng.standard_normal((n, dims[0])).astype(np.float32)
+    y = rng.integers(0, dims[-1], n).astype(np.int32)
+    m = (rng.random(n) < 0.5).astype(np.uint8)
+    w = random_weights(dims, 3, sage=True)
+    f = og.forward("sage", rowptr, colidx, dims, X, w)
+    lines = []
+    got = [a.astype(np.float32) for a in f.act]
+    plain = og.backward(f, y, m)
+    out = aligned_backward(og, f, got, w, X, y, m, 1e-4, lines.append, got_gact=plain["gact"])
+    assert any("0 of %d rows" % n in s for s in lines)
+    for a, b in zip(out["gact"], plain["gact"]):
+        assert rel_err(a, b) < 1e-12
+    # a decision flipped where the pre-activation is nowhere near zero
+    v, c = np.unravel_index(np.argmax(f.act[0]), f.act[0].shape)
+    bad = [a.copy() for a in got]
+    bad[0][v, c] = 0.0
+    with pytest.raises(AssertionError):
+        aligned_backward(og, f, bad, w, X, y, m, 1e-4)
+    neg = np.argwhere(f.act[1] == 0)
+    bad = [a.copy() for a in got]
+    bad[1][neg[0, 0], neg[0, 1]] = 1e-3 * f.act[1].max()
+    with pytest.raises(AssertionError):
+        aligned_backward(og, f, bad, w, X, y, m, 1e-4)
+    # a flip near zero that a sloppy forward pass (error 1e-3 of the maximum) would excuse
+    pos = f.act[0][f.act[0] > 0]
+    thr = np.sort(pos)[3]
+    v, c = np.argwhere(f.act[0] == thr)[0]
+    bad = [a.copy() for a in got]
+    bad[0][v, c] = 0.0
+    bad[0][0, 0] += 1e-3 * f.act[0].max()
+    with pytest.raises(AssertionError):
+        aligned_backward(og, f, bad, w, X, y, m, 1e-4)
+    assert elem_err([1.0, 1e-6], [1.0, 2e-6]) < 1.1e-3 and abs(elem_err([1.0, 0.5], [1.0, 0.4]) - 0.25) < 1e-12
