@@ -188,6 +188,8 @@ gnn_status gnn_workspace_bytes(const gnn_ctx *ctx, int64_t *staging, int64_t *sc
  *   grad_w          same layout as weights, always fp32
  *   labels [n] int32 in [0, d_L);  train_mask [n] uint8
  *   staging, scratch: at least gnn_workspace_bytes(), 256-byte aligned
+ *   feat, act[], grad_act[], the weight matrices and their gradients must be 16-byte aligned
+ *   (GNN_EINVAL otherwise): rows are read and written as 16-byte vectors
  * The pointer arrays themselves are host memory and are copied.
  *
  * Streaming schedule (hbm_budget_bytes > 0; the one-GPU analogue of the paper's partition-wise
@@ -213,9 +215,17 @@ gnn_status gnn_bind(gnn_ctx *ctx, const void *feat, void *const *act, void *cons
                     const uint8_t *train_mask, void *staging, void *scratch);
 
 /* dst[r] = src[order[r]] (to_library_order = 1) or dst[order[r]] = src[r] (= 0) for n rows
- * of row_bytes bytes each; src and dst are device buffers and must not overlap. */
+ * of row_bytes bytes each.  src and dst are device buffers, or pinned host buffers mapped for
+ * the device (hipHostMalloc; the kernel then moves the rows over the host link), and must not
+ * overlap.  Any alignment is accepted; rows are moved in 16-byte vectors when row_bytes and both
+ * addresses are multiples of 16, in narrower units otherwise. */
 gnn_status gnn_permute_rows(gnn_ctx *ctx, const void *src, void *dst, int64_t row_bytes,
                             int32_t to_library_order, void *stream);
+
+/* dst[i] = bfloat16(src[i]), round to nearest even, for count elements: how fp32 inputs and
+ * weights are put into GNN_BF16 storage (once, before the first epoch).  src (fp32) and dst
+ * (raw 16-bit) are device buffers or pinned host buffers mapped for the device. */
+gnn_status gnn_to_bf16(gnn_ctx *ctx, const float *src, void *dst, int64_t count, void *stream);
 
 /* ---- the hot path (enqueue on `stream`, do not synchronise) ---------------------------- */
 

@@ -84,6 +84,7 @@ def load_library():
         "gnn_workspace_bytes": [vp, P(i64), P(i64)],
         "gnn_bind": [vp, vp, P(vp), P(vp), P(vp), P(vp), vp, vp, vp, vp],
         "gnn_permute_rows": [vp, vp, vp, i64, i32, vp],
+        "gnn_to_bf16": [vp, vp, vp, i64, vp],
         "gnn_gather_boundary": [vp, i32, i32, vp],
         "gnn_layer_fwd": [vp, i32, i32, vp],
         "gnn_loss": [vp, vp],
@@ -224,6 +225,9 @@ class Context:
         self._check(self.lib.gnn_permute_rows(self.h, src, dst, int(row_bytes),
                                               1 if to_library_order else 0, stream))
 
+    def to_bf16(self, src, dst, count, stream):
+        self._check(self.lib.gnn_to_bf16(self.h, src, dst, int(count), stream))
+
     def gather_boundary(self, layer, p, stream):
         self._check(self.lib.gnn_gather_boundary(self.h, int(layer), int(p), stream))
 
@@ -330,19 +334,21 @@ class Session:
         self.has_bias = has_bias
         t = torch
         stream = self.stream
-        # inputs: upload in original order, permute on the device
-        # bf16 storage: values are converted once here (round to nearest even)
-        self.labels = self._to_library(t.from_numpy(np.ascontiguousarray(labels, dtype=np.int32)))
-        self.mask = self._to_library(t.from_numpy(np.ascontiguousarray(train_mask, dtype=np.uint8)))
+        # inputs: fp32 in original order -> storage type (the library's rounding to bfloat16) ->
+        # library order (the library's row permutation); torch only allocates and copies
+        self.labels = self._to_library(t.from_numpy(np.ascontiguousarray(labels, dtype=np.int32)).to(self.dev))
+        self.mask = self._to_library(t.from_numpy(np.ascontiguousarray(train_mask, dtype=np.uint8)).to(self.dev))
         if self.streaming:
-            self.order = t.from_numpy(self.ctx.get_order()[0].astype(np.int64))
+            # pinned (device-mapped) host arrays on both sides: the library's kernels read and
+            # write them over the host link
             big = dict(device="cpu", pin_memory=True)
-            self.feat = t.from_numpy(np.ascontiguousarray(X, dtype=np.float32)).to(store)[self.order] \
-                .contiguous().pin_memory()
+            src = self._store(t.from_numpy(np.ascontiguousarray(X, dtype=np.float32)).pin_memory())
+            self.feat = self._to_library(src)
+            del src
         else:
             big = dict(device=self.dev)
             self.feat = self._to_library(
-                t.from_numpy(np.ascontiguousarray(X, dtype=np.float32)).to(store))
+                self._store(t.from_numpy(np.ascontiguousarray(X, dtype=np.float32)).to(self.dev)))
         say("features placed")
         self.act, self.gact = [], []
         for l in range(self.L):
@@ -362,7 +368,7 @@ class Session:
                 if use:
                     wt = t.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(self.dev)
                     if key != "b":
-                        wt = wt.to(store)
+                        wt = self._store(wt)
                     self.w.append(wt)
                     self.gw.append(t.zeros(wt.shape, dtype=t.float32, device=self.dev))
                 else:
@@ -383,27 +389,50 @@ class Session:
     def stream(self):
         return self.torch.cuda.current_stream(self.dev).cuda_stream
 
-    def _to_library(self, host_tensor):
+    def _store(self, f32):
+        """fp32 tensor (device, or pinned host) -> the context's storage type, same placement."""
+        if not self.bf16:
+            return f32
         t = self.torch
-        src = host_tensor.to(self.dev)
-        dst = t.empty_like(src)
+        out = t.empty(f32.shape, dtype=t.bfloat16, device=f32.device, pin_memory=not f32.is_cuda)
+        self.ctx.to_bf16(f32.data_ptr(), out.data_ptr(), f32.numel(), self.stream)
+        t.cuda.synchronize()
+        return out
+
+    def _to_library(self, src):
+        """Rows in original vertex order -> library order (device tensor, or pinned host tensor)."""
+        t = self.torch
+        dst = t.empty(src.shape, dtype=src.dtype, device=src.device, pin_memory=not src.is_cuda)
         row_bytes = src.element_size() * (src.shape[1] if src.dim() == 2 else 1)
         self.ctx.permute_rows(src.data_ptr(), dst.data_ptr(), row_bytes, True, self.stream)
         t.cuda.synchronize()
         return dst
 
-    def to_original(self, dev_tensor):
-        """Tensor in library order -> numpy array in original vertex order."""
+    def to_original(self, tensor):
+        """Tensor in library order (device or pinned host) -> numpy array in original vertex order."""
         t = self.torch
-        if not dev_tensor.is_cuda:
-            out = t.empty_like(dev_tensor, pin_memory=False)
-            out[self.order] = dev_tensor
-            return out.float().numpy()
-        dst = t.empty_like(dev_tensor)
-        row_bytes = dev_tensor.element_size() * (dev_tensor.shape[1] if dev_tensor.dim() == 2 else 1)
-        self.ctx.permute_rows(dev_tensor.data_ptr(), dst.data_ptr(), row_bytes, False, self.stream)
+        dst = t.empty(tensor.shape, dtype=tensor.dtype, device=tensor.device, pin_memory=not tensor.is_cuda)
+        row_bytes = tensor.element_size() * (tensor.shape[1] if tensor.dim() == 2 else 1)
+        self.ctx.permute_rows(tensor.data_ptr(), dst.data_ptr(), row_bytes, False, self.stream)
         t.cuda.synchronize()
         return dst.float().cpu().numpy()
+
+    def set_layer_order(self, mode):
+        """Switches the layer order ("auto" / "aggregate") of a bound session: the workspace sizes
+        depend on it, so staging and scratch are allocated anew and everything is bound again."""
+        t = self.torch
+        t.cuda.synchronize()
+        self.ctx.set_layer_order(mode)
+        self.staging = self.scratch = None
+        t.cuda.empty_cache()
+        sb, wb = self.ctx.workspace_bytes()
+        self.staging = t.empty(sb, dtype=t.uint8, device=self.dev)
+        self.scratch = t.empty(wb, dtype=t.uint8, device=self.dev)
+        ptr = lambda x: x.data_ptr() if x is not None else None
+        self.ctx.bind(ptr(self.feat), [ptr(a) for a in self.act], [ptr(g) for g in self.gact],
+                      [ptr(w) for w in self.w], [ptr(g) for g in self.gw], ptr(self.labels),
+                      ptr(self.mask), ptr(self.staging), ptr(self.scratch))
+        t.cuda.synchronize()
 
     def epoch(self):
         return self.ctx.epoch(self.stream)

@@ -279,15 +279,24 @@ void compute_fwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, char*
         // gnn_epoch, resident: the contraction (and the dropout behind it) goes to the side stream
         // once Z is complete, and the caller's stream moves on to the next partition's gather
         hipEvent_t ready = c->side_events[c->side_events.size() - 3];
-        (void)hipEventRecord(ready, s);
-        (void)hipStreamWaitEvent(c->fwd_side, ready, 0);
-        s = c->fwd_side;
+        hipError_t e = hipEventRecord(ready, s);
+        if (e == hipSuccess) e = hipStreamWaitEvent(c->fwd_side, ready, 0);
+        if (e != hipSuccess) {
+            // without the dependency the contraction must not leave this stream: report the
+            // failure (check_launch picks it up) and stay on the caller's stream
+            c->deferred = e;
+        } else {
+            s = c->fwd_side;
+        }
     }
     struct Release {        // the Z region is free again when everything launched below has run
         gnn_ctx* c; hipStream_t s;
         ~Release()
         {
-            if (c->fwd_side) (void)hipEventRecord(c->side_events[c->side_events.size() - 2 + (size_t)c->z_slot], s);
+            if (c->fwd_side) {
+                hipError_t e = hipEventRecord(c->side_events[c->side_events.size() - 2 + (size_t)c->z_slot], s);
+                if (e != hipSuccess && c->deferred == hipSuccess) c->deferred = e;
+            }
         }
     } release{c, s};
     Timed t(c, s, GNN_K_GEMM_FWD);
@@ -800,9 +809,17 @@ gnn_status gnn_bind(gnn_ctx* c, const void* feat, void* const* act, void* const*
         if (c->has_bias && (!weights[3 * l + 2] || !grad_w[3 * l + 2]))
             return c->fail(GNN_EINVAL, "null bias buffer although has_bias is set");
     }
-    if ((reinterpret_cast<uintptr_t>(staging) | reinterpret_cast<uintptr_t>(scratch) |
-         reinterpret_cast<uintptr_t>(feat)) & 15)
-        return c->fail(GNN_EINVAL, "feat, staging and scratch must be 16-byte aligned");
+    // every per-vertex array and every weight matrix is read and written in 16-byte vectors
+    uintptr_t bits = reinterpret_cast<uintptr_t>(staging) | reinterpret_cast<uintptr_t>(scratch) |
+                     reinterpret_cast<uintptr_t>(feat);
+    for (int32_t l = 0; l < L; ++l) {
+        bits |= reinterpret_cast<uintptr_t>(act[l]) | reinterpret_cast<uintptr_t>(grad_act[l]);
+        for (int j = 0; j < 2; ++j)
+            bits |= reinterpret_cast<uintptr_t>(weights[3 * l + j]) | reinterpret_cast<uintptr_t>(grad_w[3 * l + j]);
+    }
+    if (bits & 15)
+        return c->fail(GNN_EINVAL, "feat, act[], grad_act[], the weight matrices and their gradients, staging and "
+                                   "scratch must be 16-byte aligned");
     gnn_status st = ensure_device(c);
     if (st != GNN_OK) return st;
     c->feat = (const char*)feat;
@@ -849,6 +866,17 @@ gnn_status gnn_permute_rows(gnn_ctx* c, const void* src, void* dst, int64_t row_
     if (to_library_order) launch_gather_rows(src, c->D.order, dst, c->M.n, row_bytes, s);
     else launch_scatter_rows(src, c->D.order, dst, c->M.n, row_bytes, s);
     return check_launch(c, "gnn_permute_rows");
+}
+
+gnn_status gnn_to_bf16(gnn_ctx* c, const float* src, void* dst, int64_t count, void* stream)
+{
+    if (!c) return GNN_EINVAL;
+    if (!src || !dst || count < 0) return c->fail(GNN_EINVAL, "bad gnn_to_bf16 arguments");
+    if ((reinterpret_cast<uintptr_t>(src) & 3) || (reinterpret_cast<uintptr_t>(dst) & 1))
+        return c->fail(GNN_EINVAL, "gnn_to_bf16: src must be 4-byte and dst 2-byte aligned");
+    if (count == 0) return GNN_OK;
+    launch_to_bf16(src, dst, count, (hipStream_t)stream);
+    return check_launch(c, "gnn_to_bf16");
 }
 
 gnn_status gnn_gather_boundary(gnn_ctx* c, int32_t layer, int32_t p, void* stream)
@@ -1173,18 +1201,38 @@ gnn_status gnn_layer_bwd(gnn_ctx* c, int32_t layer, int32_t p, void* stream)
     return check_launch(c, "gnn_layer_bwd");
 }
 
+static gnn_status epoch_resident(gnn_ctx* c, void* stream, float* loss_out);
+
 gnn_status gnn_epoch(gnn_ctx* c, void* stream, float* loss_out)
 {
     if (!c || !loss_out) return GNN_EINVAL;
     if (!c->bound) return c->fail(GNN_ESTATE, "buffers are not bound (call gnn_bind)");
-    hipStream_t s = (hipStream_t)stream;
-    const int32_t L = c->L, k = c->M.k;
     c->events_used = 0;
     if (c->streaming()) {
-        gnn_status st = epoch_streaming(c, s, loss_out);
+        gnn_status st = epoch_streaming(c, (hipStream_t)stream, loss_out);
         if (st == GNN_OK && c->prof) collect_profile(c);
         return st;
     }
+    const gnn_status st = epoch_resident(c, stream, loss_out);
+    if (st != GNN_OK) {
+        // an error exit may leave work queued on the context's side stream: the caller's stream
+        // waits for it, so that whatever the caller does next on `stream` is ordered behind it
+        c->fwd_side = nullptr;
+        c->z_slot = 0;
+        c->on_side = false;
+        if (c->side) {
+            const std::string keep = c->err;
+            if (hipStreamSynchronize(c->side) != hipSuccess) (void)hipGetLastError();
+            c->err = keep;
+        }
+    }
+    return st;
+}
+
+static gnn_status epoch_resident(gnn_ctx* c, void* stream, float* loss_out)
+{
+    hipStream_t s = (hipStream_t)stream;
+    const int32_t L = c->L, k = c->M.k;
     gnn_status st = GNN_OK;
     // Overlap (fp32 GCN / GraphSAGE): where an aggregate-first layer l sits below a transform-first
     // layer l + 1, the contractions of layer l + 1's own sweep (H_p = A_p^l W forward; grad W,

@@ -129,6 +129,8 @@ struct gnn_ctx {
     int z_slot = 0;                        // which Z region compute_fwd uses (0 outside gnn_epoch's forward)
     int64_t z_off() const { return z_slot ? ws.z2 : ws.z; }
 
+    hipError_t deferred = hipSuccess;      // failure of a HIP call inside a void helper, reported by check_launch
+
     gnn_status fail(gnn_status st, const std::string& msg) const
     {
         err = msg;
@@ -181,6 +183,8 @@ struct Timed {
 inline gnn_status check_launch(gnn_ctx* c, const char* what)
 {
     hipError_t e = hipGetLastError();
+    if (e == hipSuccess && c->deferred != hipSuccess) e = c->deferred;
+    c->deferred = hipSuccess;
     if (e != hipSuccess) return c->fail(GNN_EHIP, std::string(what) + ": " + hipGetErrorString(e));
     return GNN_OK;
 }

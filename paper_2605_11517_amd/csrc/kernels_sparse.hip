@@ -72,11 +72,14 @@ template <bool SCATTER>
 void move_rows(const void* src, const int32_t* idx, void* dst, int64_t rows, int64_t row_bytes,
                hipStream_t s)
 {
-    if (row_bytes % 16 == 0)
+    // the widest vector that divides the row and that both base addresses are aligned to
+    const uint64_t al = (uint64_t)row_bytes | (uint64_t)reinterpret_cast<uintptr_t>(src) |
+                        (uint64_t)reinterpret_cast<uintptr_t>(dst);
+    if (al % 16 == 0)
         move_rows_typed<float4, SCATTER>(src, idx, dst, rows, (int32_t)(row_bytes / 16), s);
-    else if (row_bytes % 4 == 0)
+    else if (al % 4 == 0)
         move_rows_typed<uint32_t, SCATTER>(src, idx, dst, rows, (int32_t)(row_bytes / 4), s);
-    else if (row_bytes % 2 == 0)
+    else if (al % 2 == 0)
         move_rows_typed<uint16_t, SCATTER>(src, idx, dst, rows, (int32_t)(row_bytes / 2), s);
     else
         move_rows_typed<uint8_t, SCATTER>(src, idx, dst, rows, (int32_t)row_bytes, s);

@@ -100,6 +100,18 @@ def summarize_pmc(fetch_dir: str, write_dir: str, out_path: str, command: str) -
     open(out_path, "w").write("\n".join(lines) + "\n")
 
 
+def read_taken_at(path: str):
+    """The commit a summary says it was taken at (a line 'Taken at commit <hash>'), or None."""
+    try:
+        for line in open(path):
+            m = re.match(r"Taken at commit (\w+)", line.strip())
+            if m:
+                return m.group(1)
+    except OSError:
+        pass
+    return None
+
+
 def read_traffic(path: str):
     """The per-kernel table written by ``summarize_pmc`` (or None)."""
     try:

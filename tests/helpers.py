@@ -105,10 +105,12 @@ def aligned_backward(og, fwd, got_act, weights, X, labels, mask, tol, say=None, 
     * fp32 storage: 8 x the forward error of that layer as measured here, max|got - oracle|
       over the whole tensor (taken before any alignment; the forward pass does not depend on
       the decisions), and never more than 1e-5 max|A^l|;
-    * bfloat16 storage: per element, four bfloat16 half-ulps (2^-9 each) of the magnitude
-      that was summed into it, 2^-7 (S|A^{l-1}| |W| + |A^{l-1}| |W_s| + |b|)[v, c]: the
-      aggregate (or the transformed row) is rounded to bfloat16 once before the sum and its
-      inputs once before that.
+    * bfloat16 storage: per element, from the terms that were summed into it.  The aggregate
+      (or the transformed row) is rounded to bfloat16 once before the sum and its inputs once
+      before that; each rounding moves a term t_j = z_j W_jc by at most 2^-9 |t_j|, uniformly
+      distributed, so the sum moves with a standard deviation of 2^-9 sqrt(2/3) |t|_2.  The
+      band is about 13 of those: 2^-6 sqrt(2) |t|_2 with
+      t = (S|A^{l-1}| * |W|, |A^{l-1}| * |W_s|, |b|)[v, c].
 
     Both the oracle's pre-activation and the other side's stored activation must lie inside
     the band at every disagreement, and the number of disagreements is capped (1e-6 of the
@@ -146,12 +148,12 @@ def aligned_backward(og, fwd, got_act, weights, X, labels, mask, tol, say=None, 
                 # magnitudes summed into each of these pre-activations (A^{l-1} >= 0 above layer 1)
                 zabs = np.abs(fwd.z[l][v]) if l > 0 else \
                     og.aggregate(fwd.m, fwd.rowptr, fwd.colidx, np.abs(prev))[v]
-                mag = np.einsum("ij,ji->i", zabs, np.abs(W[:, c]))
+                sq = np.einsum("ij,ji->i", zabs ** 2, W[:, c] ** 2)
                 if Ws is not None:
-                    mag = mag + np.einsum("ij,ji->i", np.abs(prev[v]), np.abs(np.asarray(Ws, dtype=np.float64)[:, c]))
+                    sq = sq + np.einsum("ij,ji->i", prev[v] ** 2, np.asarray(Ws, dtype=np.float64)[:, c] ** 2)
                 if b is not None:
-                    mag = mag + np.abs(np.asarray(b, dtype=np.float64)[c])
-                band = 2.0 ** -7 * mag
+                    sq = sq + np.asarray(b, dtype=np.float64)[c] ** 2
+                band = 2.0 ** -6 * np.sqrt(2.0 * sq)
                 band_txt = "per-element bands up to %.2g max|A|" % (float(band.max()) / amax)
             else:
                 band = 8.0 * fwd_err
