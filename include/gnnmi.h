@@ -253,7 +253,8 @@ gnn_status gnn_loss(gnn_ctx *ctx, void *stream);
  * no allocating routine is called.  Inputs and outputs are the bound ones (A^L, labels, mask ->
  * grad_act[L-1]); the scalar loss is written to loss_dev (device, one float, caller owned) on
  * `stream`; gnn_read_loss does not see it.  Same kernels and summation order as gnn_loss, so the
- * results are the same bits.  At most 67,104,768 vertices: GNN_EINVAL beyond, with a message.
+ * results are the same bits.  Limit: n / 64 + k + 2 <= 1,048,512 (about 67 million vertices):
+ * GNN_EINVAL beyond, with a message.
  * Every call on a GPU uses that GPU's one array: calls that overlap in time on one GPU (two
  * streams, two contexts, two threads) race; calls in sequence are fine, nothing is carried from
  * one call to the next.  Other errors as gnn_loss; GNN_EHIP if the array's address cannot be

@@ -36,8 +36,8 @@ GatView view(gnn_ctx* c, int32_t layer, int32_t p)
     v.dout = c->dims[(size_t)layer];
     v.dp = c->padded(layer);
     char* sc = c->scratch;
-    v.H = (float*)(sc + c->ws.h);
-    v.gH = (float*)(sc + c->ws.gh);
+    v.H = (float*)c->hbuf;
+    v.gH = (float*)c->ghbuf;
     v.ssrc = (float*)(sc + c->ws.ssrc);
     v.sdst = (float*)(sc + c->ws.sdst);
     v.gssrc = (float*)(sc + c->ws.gssrc);
@@ -126,7 +126,7 @@ void gat_bwd_begin(gnn_ctx* c, int32_t layer, hipStream_t s)
 {
     const int64_t n = c->M.n;
     Timed t(c, s, GNN_K_OTHER);
-    launch_fill_zero(c->scratch + c->ws.gh, n * (int64_t)c->padded(layer) * 4, s);
+    launch_fill_zero(c->ghbuf, n * (int64_t)c->padded(layer) * 4, s);
     launch_fill_zero(c->scratch + c->ws.gssrc, n * 4, s);
     launch_fill_zero(c->scratch + c->ws.gsdst, n * 4, s);
     // grad A^{l-1} needs no initialisation: each of its rows is written once, by grad H_p W^T

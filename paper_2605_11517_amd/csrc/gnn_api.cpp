@@ -101,8 +101,22 @@ gnn_status ensure_device(gnn_ctx* c)
     return GNN_OK;
 }
 
+// Streaming schedule: may layers transform first?  Their whole-graph buffers must leave room in
+// the HBM budget for the smallest block cache (two activation and two gradient blocks of the
+// widest layer).
+void update_stream_xf(gnn_ctx* c)
+{
+    c->stream_xf_ok = false;
+    if (!c->streaming() || !c->built || c->bf16() || c->model == GNN_GAT) return;
+    int64_t dmax = 0;
+    for (int32_t d : c->dims) dmax = std::max<int64_t>(dmax, d);
+    const int64_t blk = (std::max<int64_t>(1, c->M.stats.max_own) * dmax * 4 + 255) / 256 * 256;
+    c->stream_xf_ok = c->xf_buffer_bytes(c->M.n) + 4 * blk <= c->hbm_budget / 256 * 256;
+}
+
 void compute_workspace(gnn_ctx* c)
 {
+    update_stream_xf(c);
     const HostMeta& M = c->M;
     const int32_t L = c->L;
     int64_t max_np = M.stats.max_own, max_b = M.stats.max_boundary, max_r = 0;
@@ -148,11 +162,17 @@ void compute_workspace(gnn_ctx* c)
     for (int32_t l = 1; l <= L; ++l)
         if (c->transform_first(l)) hp = std::max<int64_t>(hp, c->padded(l));
     w.h = w.gh = 0;
+    w.h_floats = w.dyall_floats = 0;
     if (hp > 0) {
         // H is read by the forward pass only and its gradient exists in the backward pass only:
-        // one buffer serves both, except for attention, whose backward pass reads H again
-        w.h = take(M.n * hp);
-        w.gh = c->model == GNN_GAT ? take(M.n * hp) : w.h;
+        // one buffer serves both, except for attention, whose backward pass reads H again.
+        // (Streaming schedule: these whole-graph buffers come out of the HBM budget instead, see
+        // stream_engine_create.)
+        w.h_floats = M.n * hp;
+        if (!c->streaming()) {
+            w.h = take(M.n * hp);
+            w.gh = c->model == GNN_GAT ? take(M.n * hp) : w.h;
+        }
         w.wpad = take(2 * din * hp);
     }
     w.dyall = -1;
@@ -160,7 +180,10 @@ void compute_workspace(gnn_ctx* c)
         int64_t dyw = 0;
         for (int32_t l = 2; l < L; ++l)
             if (c->transform_first(l)) dyw = std::max<int64_t>(dyw, c->padded(l));
-        if (dyw > 0) w.dyall = take(M.n * dyw);
+        if (dyw > 0) {
+            w.dyall_floats = M.n * dyw;
+            if (!c->streaming()) w.dyall = take(M.n * dyw);
+        }
     }
     if (c->model == GNN_GAT) {
         w.ssrc = take(M.n);
@@ -468,7 +491,7 @@ static void refresh_padded_weights(gnn_ctx* c, int32_t layer, hipStream_t s)
 
 // Transform-first layer, forward of partition p after H = A^{l-1} W exists for every vertex:
 // Z = S_p [H_own ; staging], A_p^l = act(Z (+ A_p^{l-1} W_s) + b).
-static void xf_aggregate_fwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
+void xf_aggregate_fwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, char* out_own, hipStream_t s)
 {
     const HostMeta& M = c->M;
     const int64_t r0 = M.off[(size_t)p], np = M.off[(size_t)p + 1] - r0;
@@ -478,8 +501,8 @@ static void xf_aggregate_fwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s
     float* Z = (float*)(c->scratch + c->ws.z);
     float* segpart = (float*)(c->scratch + c->ws.segpart);
     const bool b16 = c->bf16();        // H and staging hold bfloat16 rows then; Z is fp32 either way
-    const char* H = c->scratch + c->ws.h + r0 * dp * c->es();
-    float* out = (float*)c->act[(size_t)layer - 1] + r0 * dout;
+    const char* H = c->hbuf + r0 * dp * c->es();
+    float* out = (float*)out_own;
     const float* bias = c->has_bias ? (const float*)c->w[(size_t)3 * (layer - 1) + 2] : nullptr;
     const int relu = layer < c->L ? 1 : 0;
     // Without a self term and without padding the aggregation finishes the layer itself: bias and
@@ -490,7 +513,7 @@ static void xf_aggregate_fwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s
         fin.bias = bias;
         fin.relu = relu;
     }
-    void* agg_out = direct ? (void*)(c->act[(size_t)layer - 1] + r0 * (int64_t)dout * c->act_es(layer)) : (void*)Z;
+    void* agg_out = direct ? (void*)out_own : (void*)Z;
     const int agg_out_bf16 = direct && b16 && layer < c->L ? 1 : 0;
     {
         Timed t(c, s, GNN_K_SPMM);
@@ -510,13 +533,13 @@ static void xf_aggregate_fwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s
             ep.bias = bias;
             if (b16) {
                 GemmSegBf16 seg;
-                seg.a = c->layer_input(layer, r0); seg.lda = din;
+                seg.a = in_own; seg.lda = din;
                 seg.b = c->w[(size_t)3 * (layer - 1) + 1]; seg.ldb = dout; seg.k = din;
                 launch_gemm_bf16_nn(&seg, 1, out, 0, dout, np, dout, ep, s);
             } else {
                 const PaddedW ws = padded_weight(c, layer, 1);
                 GemmSeg seg;
-                seg.a = (const float*)c->layer_input(layer, r0); seg.lda = din;
+                seg.a = (const float*)in_own; seg.lda = din;
                 seg.b = ws.p; seg.ldb = ws.ld; seg.k = din;
                 launch_gemm_nn(&seg, 1, out, dout, np, dout, ep, s);
             }
@@ -526,7 +549,7 @@ static void xf_aggregate_fwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s
     } else if (b16 && layer < c->L) {
         // hidden layer with bfloat16 storage: the output rows are rounded once, here
         Timed t(c, s, GNN_K_OTHER);
-        launch_bias_act_bf16(c->act[(size_t)layer - 1] + r0 * (int64_t)dout * 2, Z, np, dout, dp, bias, relu, s);
+        launch_bias_act_bf16(out_own, Z, np, dout, dp, bias, relu, s);
     } else {
         Timed t(c, s, GNN_K_OTHER);
         launch_add_padded(out, Z, np, dout, dp, bias, 0, relu, s);
@@ -534,14 +557,17 @@ static void xf_aggregate_fwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s
     if (c->dropout_p > 0.f && layer < c->L) {
         const uint64_t key = splitmix64(c->dropout_seed ^ splitmix64((uint64_t)(64 * c->dropout_epoch + layer)));
         const uint32_t threshold = (uint32_t)std::floor((double)c->dropout_p * 4294967296.0);
-        launch_dropout(c->act[(size_t)layer - 1] + r0 * (int64_t)dout * c->act_es(layer), b16 ? 1 : 0,
+        launch_dropout(out_own, b16 ? 1 : 0,
                        c->D.order + r0, np, dout, key, threshold, 1.f / (1.f - c->dropout_p), s);
     }
 }
 
 // Transform-first layer, backward of partition p: dY_p, bias and self-weight gradients, and
 // grad H [R_p] += S_p^T dY_p (the scatter-accumulate happens at the layer's output width).
-static void xf_aggregate_bwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
+// in_own: A_p^{l-1} (GraphSAGE only), g_own: grad A_p^l, act_own: A_p^l (hidden layers),
+// gprev_own: grad A_p^{l-1} (only where the self term is written in this sweep).
+void xf_aggregate_bwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own_c, const float* g_own,
+                      const char* act_own, float* gprev_own, hipStream_t s)
 {
     const HostMeta& M = c->M;
     const int32_t L = c->L;
@@ -551,24 +577,23 @@ static void xf_aggregate_bwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s
     float* gb = c->has_bias ? c->gw[(size_t)3 * (layer - 1) + 2] : nullptr;
     float* dYbuf = (float*)(c->scratch + c->ws.dy);
     float* colpart = (float*)(c->scratch + c->ws.colpart);
-    const float* g_own = c->gact[(size_t)layer - 1] + r0 * dout;
     const float drop_scale = c->dropout_p > 0.f ? 1.f / (1.f - c->dropout_p) : 1.f;
     if (c->bf16()) {
         // output layer with bfloat16 storage (dp == dout): dY as bfloat16, the rest as below
         {
             Timed t(c, s, GNN_K_ACT_BWD);
-            const char* act_own = layer < L ? c->act[(size_t)layer - 1] + r0 * (int64_t)dout * 2 : nullptr;
-            launch_act_bwd_bf16(g_own, act_own, dYbuf, np, dout, gb, colpart, layer < L ? drop_scale : 1.f, s);
+            launch_act_bwd_bf16(g_own, layer < L ? act_own : nullptr, dYbuf, np, dout, gb, colpart,
+                                layer < L ? drop_scale : 1.f, s);
         }
         if (c->model == GNN_SAGE_MEAN) {
             {
                 Timed t(c, s, GNN_K_GEMM_DW);
-                launch_gemm_bf16_tn(c->layer_input(layer, r0), din, dYbuf, dout, c->gw[(size_t)3 * (layer - 1) + 1],
+                launch_gemm_bf16_tn(in_own_c, din, dYbuf, dout, c->gw[(size_t)3 * (layer - 1) + 1],
                                     dout, din, dout, np, (float*)(c->scratch + c->ws.partial), s);
             }
             if (layer >= 2)
                 // (the first thing written to these rows of grad A^{l-1})
-                compute_bwd_self(c, layer, p, (const char*)dYbuf, c->gact[(size_t)layer - 2] + r0 * din, s, 0);
+                compute_bwd_self(c, layer, p, (const char*)dYbuf, gprev_own, s, 0);
         }
         const int64_t t0b = M.toff[(size_t)p];
         const SpmmItems itb = plan_items(M.plan_bwd, c->D.bwd, p);
@@ -577,7 +602,7 @@ static void xf_aggregate_bwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s
         scb.n_own = np;
         scb.base_row = r0;
         scb.idx = c->D.bnd + M.boff[(size_t)p];
-        float* gHb = (float*)(c->scratch + c->ws.gh);
+        float* gHb = (float*)c->ghbuf;
         {
             Timed t(c, s, GNN_K_SPMM_T);
             launch_spmm(c->D.trp + t0b, c->D.tcol, c->D.tw, nullptr, dYbuf, np, nullptr, gHb, np + nb, dp, 1, 0, itb,
@@ -590,21 +615,21 @@ static void xf_aggregate_bwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s
         return;
     }
     // a hidden GraphSAGE layer keeps its (padded) dY rows for the second sweep
-    float* keep = c->model == GNN_SAGE_MEAN && layer >= 2 && layer < L && c->ws.dyall >= 0
-                      ? (float*)(c->scratch + c->ws.dyall) + r0 * dp : nullptr;
+    float* keep = c->model == GNN_SAGE_MEAN && layer >= 2 && layer < L && c->dyall_buf
+                      ? c->dyall_buf + r0 * dp : nullptr;
     if (keep && dp == dout) dYbuf = keep;
     const float* dY = g_own;
     {
         Timed t(c, s, GNN_K_ACT_BWD);
         if (layer < L) {
-            launch_act_bwd(g_own, (const float*)c->act[(size_t)layer - 1] + r0 * dout, dYbuf, np, dout, gb,
+            launch_act_bwd(g_own, (const float*)act_own, dYbuf, np, dout, gb,
                            colpart, drop_scale, s);
             dY = dYbuf;
         } else {
             launch_act_bwd(g_own, nullptr, nullptr, np, dout, gb, colpart, 1.f, s);
         }
     }
-    const float* in_own = (const float*)c->layer_input(layer, r0);
+    const float* in_own = (const float*)in_own_c;
     // dY with rows padded to whole vectors (zeros in the padding): the operand of everything below
     const float* dYp = dY;
     if (dp != dout) {
@@ -627,7 +652,7 @@ static void xf_aggregate_bwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s
             const PaddedW ws = padded_weight(c, layer, 1);
             Timed t(c, s, GNN_K_GEMM_DZ);
             GemmEpilogue ep;
-            launch_gemm_nt(dYp, dp, ws.p, ws.ld, c->gact[(size_t)layer - 2] + r0 * din, din, np, din, dp, ep, s);
+            launch_gemm_nt(dYp, dp, ws.p, ws.ld, gprev_own, din, np, din, dp, ep, s);
         }
     }
     const int64_t t0 = M.toff[(size_t)p];
@@ -637,7 +662,7 @@ static void xf_aggregate_bwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s
     sc.n_own = np;
     sc.base_row = r0;
     sc.idx = c->D.bnd + M.boff[(size_t)p];
-    float* gH = (float*)(c->scratch + c->ws.gh);
+    float* gH = (float*)c->ghbuf;
     {
         Timed t(c, s, GNN_K_SPMM_T);
         launch_spmm(c->D.trp + t0, c->D.tcol, c->D.tw, nullptr, dYp, np, nullptr, gH, np + nb, dp, 0, 0, items,
@@ -647,6 +672,109 @@ static void xf_aggregate_bwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s
         Timed t(c, s, GNN_K_SPMM_REDUCE);
         launch_spmm_reduce(nullptr, gH, dp, 0, items, segpart, sc, s);
     }
+}
+
+// Transform-first layer, first sweep of the forward pass: H_p = A_p^{l-1} W (rows of partition p
+// of the whole-graph buffer H).
+void xf_transform_fwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, hipStream_t s)
+{
+    const HostMeta& M = c->M;
+    const int64_t r0 = M.off[(size_t)p], np = M.off[(size_t)p + 1] - r0;
+    const int32_t din = c->dims[(size_t)layer - 1], dout = c->dims[(size_t)layer], dp = c->padded(layer);
+    if (c->bf16()) {
+        // bfloat16 storage (dp == dout): H in bfloat16
+        Timed t(c, s, GNN_K_GEMM_FWD);
+        GemmSegBf16 seg;
+        seg.a = in_own; seg.lda = din;
+        seg.b = c->w[(size_t)3 * (layer - 1)]; seg.ldb = dout; seg.k = din;
+        launch_gemm_bf16_nn(&seg, 1, c->hbuf + r0 * dp * 2, 1, dp, np, dout, GemmEpilogue{}, s,
+                            c->scratch + c->ws.wt);
+        return;
+    }
+    float* H = (float*)c->hbuf + r0 * dp;
+    refresh_padded_weights(c, layer, s);
+    // all dp columns are computed: the padding columns of W are zero, so are those of H
+    const PaddedW w = padded_weight(c, layer, 0);
+    Timed t(c, s, GNN_K_GEMM_FWD);
+    GemmSeg seg;
+    seg.a = (const float*)in_own; seg.lda = din;
+    seg.b = w.p; seg.ldb = w.ld; seg.k = din;
+    launch_gemm_nn(&seg, 1, H, dp, np, w.ld == dp ? dp : dout, GemmEpilogue{}, s);
+}
+
+// Transform-first layer, second sweep of the backward pass, once grad H is complete:
+// grad W += A_p^{l-1 T} grad H_p, grad A_p^{l-1} = grad H_p W^T (+ dY_p W_s^T).  g_own = grad A_p^l
+// (read only by a GraphSAGE output layer, whose dY is grad A^L itself).
+void xf_transform_bwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own_c, const float* g_own,
+                      float* gprev_own, hipStream_t s)
+{
+    const HostMeta& M = c->M;
+    const int64_t r0 = M.off[(size_t)p], np = M.off[(size_t)p + 1] - r0;
+    const int32_t din = c->dims[(size_t)layer - 1], dout = c->dims[(size_t)layer], dp = c->padded(layer);
+    const float* gH = (const float*)c->ghbuf + r0 * dp;
+    if (c->bf16()) {
+        // the contractions take bfloat16 operands: grad H of this partition is rounded once
+        char* gHb = c->scratch + c->ws.dz;
+        {
+            Timed t(c, s, GNN_K_OTHER);
+            launch_to_bf16(gH, gHb, np * (int64_t)dp, s);
+        }
+        {
+            Timed t(c, s, GNN_K_GEMM_DW);
+            launch_gemm_bf16_tn(in_own_c, din, gHb, dp, c->gw[(size_t)3 * (layer - 1)], dout, din,
+                                dout, np, (float*)(c->scratch + c->ws.partial), s);
+        }
+        if (layer >= 2) {
+            Timed t(c, s, GNN_K_GEMM_DZ);
+            GemmEpilogue ep;
+            ep.accumulate = c->model == GNN_SAGE_MEAN ? 1 : 0;    // SAGE: the self term is there already
+            launch_gemm_bf16_nt(gHb, dp, c->w[(size_t)3 * (layer - 1)], dout, gprev_own, 0,
+                                din, np, din, dout, ep, s);
+        }
+        return;
+    }
+    const float* in_own = (const float*)in_own_c;
+    {
+        Timed t(c, s, GNN_K_GEMM_DW);
+        launch_gemm_tn(in_own, din, gH, dp, c->gw[(size_t)3 * (layer - 1)], dout, din, dout, np,
+                       (float*)(c->scratch + (c->on_side ? c->ws.partial2 : c->ws.partial)), s);
+    }
+    const bool kept = c->model == GNN_SAGE_MEAN && layer >= 2 && layer < c->L && c->dyall_buf;
+    if (layer >= 2 && (layer == c->L || kept) && c->model == GNN_SAGE_MEAN) {
+        // grad A^{l-1}_own = grad H_p W^T + dY_p W_s^T in one pass over the result: the output
+        // layer's dY_p is grad A^L_p, a hidden layer's padded dY_p was kept by the first sweep
+        const float* dY = kept ? c->dyall_buf + r0 * dp : g_own;
+        if (!kept && dp != dout) {
+            Timed t(c, s, GNN_K_OTHER);
+            float* pad = (float*)(c->scratch + c->ws.dz);
+            launch_pad_rows(pad, dY, np, dout, dp, s);
+            dY = pad;
+        }
+        const PaddedW w = padded_weight(c, layer, 0), ws = padded_weight(c, layer, 1);
+        Timed t(c, s, GNN_K_GEMM_DZ);
+        GemmSeg seg[2];
+        seg[0].a = gH; seg[0].lda = dp; seg[0].b = w.p; seg[0].ldb = w.ld; seg[0].k = dp;
+        seg[1].a = dY; seg[1].lda = dp; seg[1].b = ws.p; seg[1].ldb = ws.ld; seg[1].k = dp;
+        launch_gemm_nt2(seg, 2, gprev_own, din, np, din, GemmEpilogue{}, s);
+    } else if (layer >= 2) {
+        const PaddedW w = padded_weight(c, layer, 0);
+        Timed t(c, s, GNN_K_GEMM_DZ);
+        GemmEpilogue ep;
+        ep.accumulate = c->model == GNN_SAGE_MEAN ? 1 : 0;    // SAGE: the self term is there already
+        launch_gemm_nt(gH, dp, w.p, w.ld, gprev_own, din, np, din, dp, ep, s);
+    }
+}
+
+// Start of a transform-first layer's backward pass: grad H := 0 (it takes the buffer H was in).
+void xf_begin_bwd(gnn_ctx* c, int32_t layer, hipStream_t s)
+{
+    {
+        Timed t(c, s, GNN_K_OTHER);
+        launch_fill_zero(c->ghbuf, c->M.n * (int64_t)c->padded(layer) * 4, s);
+        // grad A^{l-1} needs no initialisation here: each of its rows is written once (by
+        // the self term, else by grad H W^T) before anything is added to it
+    }
+    refresh_padded_weights(c, layer, s);
 }
 
 }  // namespace gnnmi
@@ -839,6 +967,15 @@ gnn_status gnn_bind(gnn_ctx* c, const void* feat, void* const* act, void* const*
     c->mask = train_mask;
     c->staging = (char*)staging;
     c->scratch = (char*)scratch;
+    // whole-graph buffers of transform-first layers: in scratch (resident schedule) or given out
+    // of the HBM budget by the streaming engine below
+    c->hbuf = c->ghbuf = nullptr;
+    c->dyall_buf = nullptr;
+    if (!c->streaming() && c->ws.h_floats > 0) {
+        c->hbuf = c->scratch + c->ws.h;
+        c->ghbuf = c->scratch + c->ws.gh;
+        if (c->ws.dyall >= 0) c->dyall_buf = (float*)(c->scratch + c->ws.dyall);
+    }
     c->staged_layer = c->staged_p = -1;
     c->loss_done = false;
     std::fill(c->fwd_done.begin(), c->fwd_done.end(), 0);
@@ -898,7 +1035,7 @@ gnn_status gnn_gather_boundary(gnn_ctx* c, int32_t layer, int32_t p, void* strea
             return check_launch(c, "gnn_gather_boundary");
         }
         Timed t(c, s, GNN_K_GATHER);
-        launch_gather_rows(c->scratch + c->ws.h, c->D.bnd + b0, c->staging, nb, (int64_t)c->padded(layer) * c->es(), s);
+        launch_gather_rows(c->hbuf, c->D.bnd + b0, c->staging, nb, (int64_t)c->padded(layer) * c->es(), s);
     } else {
         const int64_t row_bytes = (int64_t)c->dims[(size_t)layer - 1] * c->es();
         Timed t(c, s, GNN_K_GATHER);
@@ -922,7 +1059,8 @@ gnn_status gnn_layer_fwd(gnn_ctx* c, int32_t layer, int32_t p, void* stream)
     if (c->model == GNN_GAT)
         gat_layer_fwd(c, layer, p, s);
     else if (c->transform_first(layer))
-        xf_aggregate_fwd(c, layer, p, s);
+        xf_aggregate_fwd(c, layer, p, c->layer_input(layer, r0),
+                         c->act[(size_t)layer - 1] + r0 * (int64_t)dout * c->act_es(layer), s);
     else
         compute_fwd(c, layer, p, c->layer_input(layer, r0),
                     c->act[(size_t)layer - 1] + r0 * (int64_t)dout * c->act_es(layer), s);
@@ -962,35 +1100,8 @@ gnn_status gnn_layer_transform_fwd(gnn_ctx* c, int32_t layer, int32_t p, void* s
         std::fill(c->xf_fwd_done.begin(), c->xf_fwd_done.end(), 0);
         c->h_layer = layer;
     }
-    if (c->model == GNN_GAT) {
-        gat_transform_fwd(c, layer, p, s);
-        c->xf_fwd_done[(size_t)(layer - 1) * (size_t)M.k + (size_t)p] = 1;
-        return check_launch(c, "gnn_layer_transform_fwd");
-    }
-    const int64_t r0 = M.off[(size_t)p], np = M.off[(size_t)p + 1] - r0;
-    const int32_t din = c->dims[(size_t)layer - 1], dout = c->dims[(size_t)layer], dp = c->padded(layer);
-    if (c->bf16()) {
-        // bfloat16 storage (dp == dout): H in bfloat16
-        Timed t(c, s, GNN_K_GEMM_FWD);
-        GemmSegBf16 seg;
-        seg.a = c->layer_input(layer, r0); seg.lda = din;
-        seg.b = c->w[(size_t)3 * (layer - 1)]; seg.ldb = dout; seg.k = din;
-        launch_gemm_bf16_nn(&seg, 1, c->scratch + c->ws.h + r0 * dp * 2, 1, dp, np, dout, GemmEpilogue{}, s,
-                            c->scratch + c->ws.wt);
-        c->xf_fwd_done[(size_t)(layer - 1) * (size_t)M.k + (size_t)p] = 1;
-        return check_launch(c, "gnn_layer_transform_fwd");
-    }
-    float* H = (float*)(c->scratch + c->ws.h) + r0 * dp;
-    refresh_padded_weights(c, layer, s);
-    {
-        // all dp columns are computed: the padding columns of W are zero, so are those of H
-        const PaddedW w = padded_weight(c, layer, 0);
-        Timed t(c, s, GNN_K_GEMM_FWD);
-        GemmSeg seg;
-        seg.a = (const float*)c->layer_input(layer, r0); seg.lda = din;
-        seg.b = w.p; seg.ldb = w.ld; seg.k = din;
-        launch_gemm_nn(&seg, 1, H, dp, np, w.ld == dp ? dp : dout, GemmEpilogue{}, s);
-    }
+    if (c->model == GNN_GAT) gat_transform_fwd(c, layer, p, s);
+    else xf_transform_fwd(c, layer, p, c->layer_input(layer, M.off[(size_t)p]), s);
     c->xf_fwd_done[(size_t)(layer - 1) * (size_t)M.k + (size_t)p] = 1;
     return check_launch(c, "gnn_layer_transform_fwd");
 }
@@ -1007,64 +1118,11 @@ gnn_status gnn_layer_transform_bwd(gnn_ctx* c, int32_t layer, int32_t p, void* s
     const HostMeta& M = c->M;
     if (c->model == GNN_GAT) {
         gat_transform_bwd(c, layer, p, s);
-        c->xf_bwd_done[(size_t)(layer - 1) * (size_t)M.k + (size_t)p] = 1;
-        return check_launch(c, "gnn_layer_transform_bwd");
-    }
-    const int64_t r0 = M.off[(size_t)p], np = M.off[(size_t)p + 1] - r0;
-    const int32_t din = c->dims[(size_t)layer - 1], dout = c->dims[(size_t)layer], dp = c->padded(layer);
-    const float* gH = (const float*)(c->scratch + c->ws.gh) + r0 * dp;
-    if (c->bf16()) {
-        // the contractions take bfloat16 operands: grad H of this partition is rounded once
-        char* gHb = c->scratch + c->ws.dz;
-        {
-            Timed t(c, s, GNN_K_OTHER);
-            launch_to_bf16(gH, gHb, np * (int64_t)dp, s);
-        }
-        {
-            Timed t(c, s, GNN_K_GEMM_DW);
-            launch_gemm_bf16_tn(c->layer_input(layer, r0), din, gHb, dp, c->gw[(size_t)3 * (layer - 1)], dout, din,
-                                dout, np, (float*)(c->scratch + c->ws.partial), s);
-        }
-        if (layer >= 2) {
-            Timed t(c, s, GNN_K_GEMM_DZ);
-            GemmEpilogue ep;
-            ep.accumulate = c->model == GNN_SAGE_MEAN ? 1 : 0;    // SAGE: the self term is there already
-            launch_gemm_bf16_nt(gHb, dp, c->w[(size_t)3 * (layer - 1)], dout, c->gact[(size_t)layer - 2] + r0 * din, 0,
-                                din, np, din, dout, ep, s);
-        }
-        c->xf_bwd_done[(size_t)(layer - 1) * (size_t)M.k + (size_t)p] = 1;
-        return check_launch(c, "gnn_layer_transform_bwd");
-    }
-    const float* in_own = (const float*)c->layer_input(layer, r0);
-    {
-        Timed t(c, s, GNN_K_GEMM_DW);
-        launch_gemm_tn(in_own, din, gH, dp, c->gw[(size_t)3 * (layer - 1)], dout, din, dout, np,
-                       (float*)(c->scratch + (c->on_side ? c->ws.partial2 : c->ws.partial)), s);
-    }
-    const bool kept = c->model == GNN_SAGE_MEAN && layer >= 2 && layer < c->L && c->ws.dyall >= 0;
-    if (layer >= 2 && (layer == c->L || kept) && c->model == GNN_SAGE_MEAN) {
-        // grad A^{l-1}_own = grad H_p W^T + dY_p W_s^T in one pass over the result: the output
-        // layer's dY_p is grad A^L_p, a hidden layer's padded dY_p was kept by the first sweep
-        const float* dY = kept ? (const float*)(c->scratch + c->ws.dyall) + r0 * dp
-                               : c->gact[(size_t)layer - 1] + r0 * dout;
-        if (!kept && dp != dout) {
-            Timed t(c, s, GNN_K_OTHER);
-            float* pad = (float*)(c->scratch + c->ws.dz);
-            launch_pad_rows(pad, dY, np, dout, dp, s);
-            dY = pad;
-        }
-        const PaddedW w = padded_weight(c, layer, 0), ws = padded_weight(c, layer, 1);
-        Timed t(c, s, GNN_K_GEMM_DZ);
-        GemmSeg seg[2];
-        seg[0].a = gH; seg[0].lda = dp; seg[0].b = w.p; seg[0].ldb = w.ld; seg[0].k = dp;
-        seg[1].a = dY; seg[1].lda = dp; seg[1].b = ws.p; seg[1].ldb = ws.ld; seg[1].k = dp;
-        launch_gemm_nt2(seg, 2, c->gact[(size_t)layer - 2] + r0 * din, din, np, din, GemmEpilogue{}, s);
-    } else if (layer >= 2) {
-        const PaddedW w = padded_weight(c, layer, 0);
-        Timed t(c, s, GNN_K_GEMM_DZ);
-        GemmEpilogue ep;
-        ep.accumulate = c->model == GNN_SAGE_MEAN ? 1 : 0;    // SAGE: the self term is there already
-        launch_gemm_nt(gH, dp, w.p, w.ld, c->gact[(size_t)layer - 2] + r0 * din, din, np, din, dp, ep, s);
+    } else {
+        const int64_t r0 = M.off[(size_t)p];
+        xf_transform_bwd(c, layer, p, c->layer_input(layer, r0),
+                         c->gact[(size_t)layer - 1] + r0 * c->dims[(size_t)layer],
+                         layer >= 2 ? c->gact[(size_t)layer - 2] + r0 * c->dims[(size_t)layer - 1] : nullptr, s);
     }
     c->xf_bwd_done[(size_t)(layer - 1) * (size_t)M.k + (size_t)p] = 1;
     return check_launch(c, "gnn_layer_transform_bwd");
@@ -1082,7 +1140,7 @@ gnn_status gnn_loss(gnn_ctx* c, void* stream)
     {
         Timed t(c, s, GNN_K_LOSS);
         launch_loss((const float*)c->act[(size_t)c->L - 1], c->labels, c->mask, c->gact[(size_t)c->L - 1],
-                    c->M.n, c->dims[(size_t)c->L], (unsigned long long*)(scal + 16),
+                    c->M.n, c->dims[(size_t)c->L], c->M.off.data(), c->M.k, (unsigned long long*)(scal + 16),
                     (float*)(c->scratch + c->ws.losspart), scal, s);
     }
     c->loss_done = true;
@@ -1097,15 +1155,16 @@ gnn_status gnn_loss_static(gnn_ctx* c, void* stream, float* loss_dev)
     if (c->streaming()) return c->fail(GNN_EUNSUPPORTED, "with a streaming budget only gnn_epoch drives the schedule");
     for (uint8_t f : c->fwd_done)
         if (!f) return c->fail(GNN_ESTATE, "gnn_loss_static before the forward pass has covered every (layer, partition)");
-    if (c->M.n > loss_static_max_rows())
-        return c->fail(GNN_EINVAL, "gnn_loss_static: " + std::to_string(c->M.n) + " vertices exceed the limit of " +
-                                       std::to_string(loss_static_max_rows()) + " the static scratch array is sized for");
+    if (loss_partial_floats(c->M.n, c->M.k) > loss_static_max_partials())
+        return c->fail(GNN_EINVAL, "gnn_loss_static: " + std::to_string(c->M.n) + " vertices in " + std::to_string(c->M.k) +
+                                       " partitions need more block partial sums (one per 64 rows of a partition) than "
+                                       "the static scratch array holds (" + std::to_string(loss_static_max_partials()) + ")");
     hipStream_t s = (hipStream_t)stream;
     hipError_t e;
     {
         Timed t(c, s, GNN_K_LOSS);
         e = launch_loss_static((const float*)c->act[(size_t)c->L - 1], c->labels, c->mask, c->gact[(size_t)c->L - 1],
-                               c->M.n, c->dims[(size_t)c->L], loss_dev, s);
+                               c->M.n, c->dims[(size_t)c->L], c->M.off.data(), c->M.k, loss_dev, s);
     }
     if (e != hipSuccess) return c->fail(GNN_EHIP, std::string("gnn_loss_static: ") + hipGetErrorString(e));
     c->loss_done = true;
@@ -1151,19 +1210,19 @@ gnn_status gnn_layer_bwd(gnn_ctx* c, int32_t layer, int32_t p, void* stream)
     if (c->transform_first(layer)) {
         // no regather and no recompute: the layer aggregated H, whose gradient is accumulated here
         if (c->bwd_done[(size_t)layer] == 0) {
-            {
-                Timed t(c, s, GNN_K_OTHER);
-                launch_fill_zero(c->scratch + c->ws.gh, c->M.n * (int64_t)c->padded(layer) * 4, s);
-                // grad A^{l-1} needs no initialisation here: each of its rows is written once (by
-                // the self term, else by grad H W^T) before anything is added to it
-            }
-            refresh_padded_weights(c, layer, s);
+            xf_begin_bwd(c, layer, s);
             // grad H takes the buffer H was in
             c->h_layer = 0;
             std::fill(c->xf_fwd_done.begin(), c->xf_fwd_done.end(), 0);
             for (int32_t q = 0; q < c->M.k; ++q) c->xf_bwd_done[(size_t)(layer - 1) * (size_t)c->M.k + (size_t)q] = 0;
         }
-        xf_aggregate_bwd(c, layer, p, s);
+        {
+            const int64_t r0x = c->M.off[(size_t)p];
+            const int32_t dl = c->dims[(size_t)layer], dprev = c->dims[(size_t)layer - 1];
+            xf_aggregate_bwd(c, layer, p, c->layer_input(layer, r0x), c->gact[(size_t)layer - 1] + r0x * dl,
+                             c->act[(size_t)layer - 1] + r0x * (int64_t)dl * c->act_es(layer),
+                             layer >= 2 ? c->gact[(size_t)layer - 2] + r0x * dprev : nullptr, s);
+        }
         c->bwd_done[(size_t)layer] += 1;
         return check_launch(c, "gnn_layer_bwd");
     }

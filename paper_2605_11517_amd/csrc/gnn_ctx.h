@@ -2,6 +2,7 @@
 // schedule.
 #pragma once
 
+#include <algorithm>
 #include <memory>
 #include <string>
 #include <vector>
@@ -40,6 +41,8 @@ struct Workspace {  // byte offsets into `scratch`
     int64_t z = 0, dy = 0, dz = 0, dga = 0, partial = 0, colpart = 0, losspart = 0, scalars = 0,
             segpart = 0;
     int64_t h = 0, gh = 0;     // transform-first layers: H = A W and its gradient, n x padded width
+    int64_t h_floats = 0;      // size of that buffer (0: no layer transforms first); the streaming
+    int64_t dyall_floats = 0;  // schedule takes it, and the kept dY rows, out of its HBM budget
     int64_t wpad = 0;          // and copies of W, W_s with rows padded to that width (2 x d_in x padded)
     int64_t wt = 0;            // bfloat16 storage: room for one transposed weight matrix
     // fp32 GraphSAGE with hidden transform-first layers: dY of every partition (n x padded width)
@@ -85,13 +88,27 @@ struct gnn_ctx {
     const uint8_t* mask = nullptr;
     char* staging = nullptr;
     char* scratch = nullptr;
+    // whole-graph buffers of transform-first layers (set by gnn_bind): H, grad H, kept dY rows
+    char* hbuf = nullptr;
+    char* ghbuf = nullptr;
+    float* dyall_buf = nullptr;
     // layer order: 0 = aggregate, then transform (the paper's); 1 = transform first in layers
     // where that moves fewer rows (resident schedule)
     int32_t order_mode = 0;
     bool transform_first(int32_t layer) const
     {
         if (model == GNN_GAT) return true;       // attention scores are taken from H = A W
-        if (order_mode != 1 || streaming()) return false;
+        if (order_mode != 1) return false;
+        // streaming schedule: fp32 only, and only when the whole-graph buffers of such layers
+        // (H / grad H, kept dY rows) fit into the HBM budget beside a minimal block cache
+        if (streaming() && (bf16() || !stream_xf_ok)) return false;
+        return wants_transform_first(layer);
+    }
+    // the cost rule alone
+    bool wants_transform_first(int32_t layer) const
+    {
+        if (model == GNN_GAT) return true;
+        if (order_mode != 1) return false;
         const int64_t din = dims[(size_t)layer - 1], dout = dims[(size_t)layer];
         // bfloat16 storage: rows of H must be whole 16-byte vectors; a hidden layer's self term
         // (GraphSAGE) would need an fp32 copy of its output rows, so there only the output layer
@@ -101,6 +118,18 @@ struct gnn_ctx {
         // >= 2); transforming first aggregates once forward and once transposed, at the output
         // width, and regathers nothing.
         return 2 * dout < din * (layer >= 2 ? 3 : 2);
+    }
+    bool stream_xf_ok = false;               // set by update_stream_xf() once the partitions exist
+    // bytes of the whole-graph buffers the transform-first layers (by the cost rule) would need
+    int64_t xf_buffer_bytes(int64_t n) const
+    {
+        int64_t hp = 0, dyw = 0;
+        for (int32_t l = 1; l <= L; ++l)
+            if (wants_transform_first(l)) {
+                hp = std::max<int64_t>(hp, padded(l));
+                if (model == GNN_SAGE_MEAN && l >= 2 && l < L) dyw = std::max<int64_t>(dyw, padded(l));
+            }
+        return (n * hp * 4 + 255) / 256 * 256 + (n * dyw * 4 + 255) / 256 * 256;
     }
     // width of H rows: d_layer rounded up to whole 16-byte vectors
     int32_t padded(int32_t layer) const { return (dims[(size_t)layer] + 3) / 4 * 4; }
@@ -209,6 +238,16 @@ const char* compute_bwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own
 // SAGE self term: gprev_own (n_p x d_{l-1} fp32) += dY_p W_s^T
 void compute_bwd_self(gnn_ctx* c, int32_t layer, int32_t p, const char* dY, float* gprev_own,
                       hipStream_t s, int accumulate = 1);
+
+// Transform-first layers on explicit row blocks (H, grad H and the kept dY rows are the
+// context's whole-graph buffers): the two sweeps of the forward and of the backward pass.
+void xf_transform_fwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, hipStream_t s);
+void xf_aggregate_fwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, char* out_own, hipStream_t s);
+void xf_begin_bwd(gnn_ctx* c, int32_t layer, hipStream_t s);
+void xf_aggregate_bwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, const float* g_own,
+                      const char* act_own, float* gprev_own, hipStream_t s);
+void xf_transform_bwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, const float* g_own,
+                      float* gprev_own, hipStream_t s);
 
 void zero_weight_grads(gnn_ctx* c, hipStream_t s);
 SpmmItems plan_items(const HostMeta::Plan& H, const DevMeta::Plan& P, int32_t p);

@@ -201,9 +201,10 @@ int64_t act_bwd_partial_floats(int64_t rows, int32_t d);
 
 // softmax cross-entropy over masked rows; grad[n, c]; *loss_dev = mean loss.  count_dev
 // receives |M| (counted on the device in the same call).
+// part_off[k + 1] (host): the rows are processed partition by partition.
 void launch_loss(const float* logits, const int32_t* labels, const uint8_t* mask, float* grad,
-                 int64_t n, int32_t c, unsigned long long* count_dev, float* partial,
-                 float* loss_dev, hipStream_t s);
+                 int64_t n, int32_t c, const int64_t* part_off, int32_t k, unsigned long long* count_dev,
+                 float* partial, float* loss_dev, hipStream_t s);
 int64_t loss_partial_floats(int64_t n, int32_t k);
 // the same in three steps, so that the rows can be processed block by block
 void launch_count_mask(const uint8_t* mask, int64_t n, unsigned long long* count_dev, hipStream_t s);
@@ -214,10 +215,12 @@ void launch_loss_finish(const float* partial, int64_t nparts, const unsigned lon
                         float* loss_dev, hipStream_t s);
 
 // The same loss with |M| and the block partial sums in a device array the library holds
-// statically (no workspace from the caller, no allocation); n <= loss_static_max_rows().
-int64_t loss_static_max_rows();
+// statically (no workspace from the caller, no allocation); loss_partial_floats(n, k) must not
+// exceed loss_static_max_partials().
+int64_t loss_static_max_partials();
 hipError_t launch_loss_static(const float* logits, const int32_t* labels, const uint8_t* mask, float* grad,
-                              int64_t n, int32_t c, float* loss_dev, hipStream_t s);
+                              int64_t n, int32_t c, const int64_t* part_off, int32_t k, float* loss_dev,
+                              hipStream_t s);
 
 void launch_fill_zero(void* p, int64_t bytes, hipStream_t s);
 

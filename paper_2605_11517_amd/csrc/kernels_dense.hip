@@ -457,11 +457,18 @@ void launch_loss_finish(const float* partial, int64_t nparts, const unsigned lon
 }
 
 void launch_loss(const float* logits, const int32_t* labels, const uint8_t* mask, float* grad,
-                 int64_t n, int32_t c, unsigned long long* count_dev, float* partial,
-                 float* loss_dev, hipStream_t s)
+                 int64_t n, int32_t c, const int64_t* part_off, int32_t k, unsigned long long* count_dev,
+                 float* partial, float* loss_dev, hipStream_t s)
 {
     launch_count_mask(mask, n, count_dev, s);
-    const int64_t blocks = launch_loss_rows(logits, labels, mask, grad, n, c, count_dev, partial, s);
+    // partition by partition, so that the block partial sums group the rows exactly as the
+    // streaming schedule does (which sees one partition block at a time): same bits in both
+    int64_t blocks = 0;
+    for (int32_t p = 0; p < k; ++p) {
+        const int64_t r0 = part_off[p], np = part_off[p + 1] - r0;
+        blocks += launch_loss_rows(logits + r0 * c, labels + r0, mask + r0, grad + r0 * c, np, c, count_dev,
+                                   partial + blocks, s);
+    }
     launch_loss_finish(partial, blocks, count_dev, loss_dev, s);
 }
 
@@ -479,14 +486,11 @@ constexpr int kMaxDevices = 64;
 void* g_static_ptr[kMaxDevices] = {};
 }  // namespace
 
-int64_t loss_static_max_rows()
-{
-    const int64_t rpb = kLossRowsPerWave * (kBlock / kWave);
-    return (kStaticScratchBytes - kStaticPartialOffset) / (int64_t)sizeof(float) * rpb;
-}
+int64_t loss_static_max_partials() { return (kStaticScratchBytes - kStaticPartialOffset) / (int64_t)sizeof(float); }
 
 hipError_t launch_loss_static(const float* logits, const int32_t* labels, const uint8_t* mask, float* grad,
-                              int64_t n, int32_t c, float* loss_dev, hipStream_t s)
+                              int64_t n, int32_t c, const int64_t* part_off, int32_t k, float* loss_dev,
+                              hipStream_t s)
 {
     int dev = -1;
     hipError_t e = hipGetDevice(&dev);
@@ -504,7 +508,7 @@ hipError_t launch_loss_static(const float* logits, const int32_t* labels, const 
     float* partial = reinterpret_cast<float*>(base + kStaticPartialOffset);
     // the count is cleared by a fill kernel inside launch_loss; the partial sums of this call's
     // blocks are all overwritten before the last kernel reads exactly that many
-    launch_loss(logits, labels, mask, grad, n, c, count_dev, partial, loss_dev, s);
+    launch_loss(logits, labels, mask, grad, n, c, part_off, k, count_dev, partial, loss_dev, s);
     return hipGetLastError();
 }
 

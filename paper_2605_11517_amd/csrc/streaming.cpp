@@ -93,14 +93,16 @@ struct StreamEngine {
     int64_t h2d_bytes = 0, d2h_bytes = 0;   // of the running epoch
     int64_t direct_gathers = 0, direct_bytes = 0;   // boundary rows read straight from host memory
     int64_t loads[2] = {0, 0}, hits[2] = {0, 0}, writebacks = 0;
-    char* io = nullptr;             // 6 transfer buffers
+    char* io = nullptr;             // 8 transfer buffers
     int64_t io_bytes = 0;           // bytes of one buffer
+    char* xf = nullptr;             // whole-graph buffers of transform-first layers (H / grad H, kept dY)
     hipEvent_t out_ready[2]{}, out_done[2]{}, in_ready[2]{}, in_released[2]{};
     hipEvent_t layer_done = nullptr, compute_done = nullptr;
     bool has_out_done[2] = {false, false}, has_in_released[2] = {false, false};
     char* outbuf(int i) const { return io + (int64_t)i * io_bytes; }
     char* ginbuf(int i) const { return io + (int64_t)(2 + i) * io_bytes; }
     char* ainbuf(int i) const { return io + (int64_t)(4 + i) * io_bytes; }
+    char* xinbuf(int i) const { return io + (int64_t)(6 + i) * io_bytes; }   // A^{l-1} blocks of such layers
 };
 
 namespace {
@@ -577,7 +579,12 @@ gnn_status stream_engine_create(gnn_ctx* c)
     int64_t dmax = 0;
     for (int32_t d : c->dims) dmax = std::max<int64_t>(dmax, d);
     E->io_bytes = round256(M.stats.max_own * dmax * 4);
-    E->pool_bytes = c->hbm_budget / 256 * 256;
+    // transform-first layers keep H (then grad H) and, for hidden GraphSAGE layers, the dY rows of
+    // every partition on the device for a whole layer pass: that comes out of the budget first
+    int64_t xf_bytes = 0;
+    for (int32_t l = 1; l <= c->L; ++l)
+        if (c->transform_first(l)) xf_bytes = c->xf_buffer_bytes(M.n);
+    E->pool_bytes = c->hbm_budget / 256 * 256 - xf_bytes;
     // the tightest layer must still fit two activation blocks and two gradient blocks
     const int64_t need = 2 * round256(M.stats.max_own * dmax * c->es()) + 2 * round256(M.stats.max_own * dmax * 4);
     if (E->pool_bytes < need) {
@@ -598,7 +605,13 @@ gnn_status stream_engine_create(gnn_ctx* c)
     if ((e = hipStreamCreateWithFlags(&E->h2d, hipStreamNonBlocking)) != hipSuccess) return fail_hip(e, "hipStreamCreate");
     if ((e = hipStreamCreateWithFlags(&E->d2h, hipStreamNonBlocking)) != hipSuccess) return fail_hip(e, "hipStreamCreate");
     if ((e = hipMalloc((void**)&E->pool, (size_t)E->pool_bytes)) != hipSuccess) return fail_hip(e, "hipMalloc(block cache)");
-    if ((e = hipMalloc((void**)&E->io, (size_t)(6 * E->io_bytes))) != hipSuccess) return fail_hip(e, "hipMalloc(transfer buffers)");
+    if ((e = hipMalloc((void**)&E->io, (size_t)(8 * E->io_bytes))) != hipSuccess) return fail_hip(e, "hipMalloc(transfer buffers)");
+    if (xf_bytes > 0) {
+        if ((e = hipMalloc((void**)&E->xf, (size_t)xf_bytes)) != hipSuccess) return fail_hip(e, "hipMalloc(transform-first buffers)");
+        const int64_t hbytes = (c->ws.h_floats * 4 + 255) / 256 * 256;
+        c->hbuf = c->ghbuf = E->xf;
+        c->dyall_buf = c->ws.dyall_floats > 0 ? (float*)(E->xf + hbytes) : nullptr;
+    }
     E->free_list.assign(1, {0, E->pool_bytes});
     for (int i = 0; i < 2; ++i) {
         if ((e = hipEventCreateWithFlags(&E->out_ready[i], hipEventDisableTiming)) != hipSuccess) return fail_hip(e, "hipEventCreate");
@@ -639,6 +652,9 @@ void stream_engine_destroy(gnn_ctx* c)
     if (E->compute_done) (void)hipEventDestroy(E->compute_done);
     if (E->pool) (void)hipFree(E->pool);
     if (E->io) (void)hipFree(E->io);
+    if (E->xf) (void)hipFree(E->xf);
+    c->hbuf = c->ghbuf = nullptr;
+    c->dyall_buf = nullptr;
     if (E->h2d) (void)hipStreamDestroy(E->h2d);
     if (E->d2h) (void)hipStreamDestroy(E->d2h);
     delete E;
@@ -722,10 +738,130 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
         return std::max<int64_t>(1, max_np) * (int64_t)c->dims[(size_t)layer] * 4;
     };
 
+    // Loads rows of a host array into transfer buffer `dst` on the load stream.
+    auto load_in = [&](char* dst, const char* src, int64_t bytes, int ib, bool first) -> gnn_status {
+        if (first && E.has_in_released[ib]) GNN_HIP(hipStreamWaitEvent(E.h2d, E.in_released[ib], 0));
+        if (bytes > 0) GNN_HIP(hipMemcpyAsync(dst, src, (size_t)bytes, hipMemcpyHostToDevice, E.h2d));
+        E.h2d_bytes += bytes;
+        return GNN_OK;
+    };
+    // One sweep over the partitions of a transform-first layer.  want(t, i) names the host rows of
+    // input block i (0: grad A^l, 1: A^l, 2: A^{l-1}) of step t unless the block is in the pool
+    // already (then it sets *dev); body(t, ptrs) enqueues the step's kernels.  The blocks of
+    // step t + 1 are loaded into the other set of transfer buffers while step t computes.
+    struct BlockReq {
+        const char* host = nullptr;   // rows to load, or null
+        int64_t bytes = 0;
+        const char* dev = nullptr;    // where the kernels find the block
+        Resident* arr = nullptr;      // block `part` of a whole array: the step waits for its load
+        int32_t part = -1;
+    };
+    auto xf_sweep = [&](auto&& want, auto&& body) -> gnn_status {
+        std::vector<BlockReq> req((size_t)3 * 2);
+        auto stage = [&](int32_t t) -> gnn_status {
+            const int ib = t & 1;
+            bool first = true;
+            for (int i = 0; i < 3; ++i) {
+                BlockReq& r = req[(size_t)ib * 3 + (size_t)i];
+                r = BlockReq{};
+                gnn_status r_st = want(t, i, r);
+                if (r_st != GNN_OK) return r_st;
+                if (!r.host) continue;
+                char* buf = i == 0 ? E.ginbuf(ib) : i == 1 ? E.ainbuf(ib) : E.xinbuf(ib);
+                if ((r_st = load_in(buf, r.host, r.bytes, ib, first)) != GNN_OK) return r_st;
+                first = false;
+                r.dev = buf;
+            }
+            GNN_HIP(hipEventRecord(E.in_ready[ib], E.h2d));
+            return GNN_OK;
+        };
+        gnn_status r_st = stage(0);
+        if (r_st != GNN_OK) return r_st;
+        for (int32_t t = 0; t < k; ++t) {
+            const int ib = t & 1;
+            if (t + 1 < k && (r_st = stage(t + 1)) != GNN_OK) return r_st;
+            GNN_HIP(hipStreamWaitEvent(s, E.in_ready[ib], 0));
+            for (int i = 0; i < 3; ++i) {
+                BlockReq& r = req[(size_t)ib * 3 + (size_t)i];
+                int32_t slot;
+                if (r.arr && (r_st = acquire(c, E, r.arr->bc, r.part, s, true, &slot)) != GNN_OK) return r_st;
+            }
+            if ((r_st = body(t, &req[(size_t)ib * 3])) != GNN_OK) return r_st;
+            GNN_HIP(hipEventRecord(E.in_released[ib], s));
+            E.has_in_released[ib] = true;
+        }
+        return GNN_OK;
+    };
+    // a block of a whole array in the pool: its load is issued here (first use) and the step
+    // that reads it waits for it
+    auto from_array = [&](Resident* r, int32_t p, BlockReq& out) -> gnn_status {
+        int32_t slot;
+        gnn_status r_st = acquire(c, E, r->bc, p, s, false, &slot);
+        if (r_st != GNN_OK) return r_st;
+        out.dev = r->bc.ptr(slot);
+        out.arr = r;
+        out.part = p;
+        return GNN_OK;
+    };
+
     // ---------------------------------------------------------------------------- forward
     for (int32_t l = 1; l <= L; ++l) {
         const int32_t dout = c->dims[(size_t)l];
         const Key keep[2] = {{ARR_ACT, l - 1}, {ARR_ACT, l}};
+        if (c->transform_first(l)) {
+            // Transform-first layer: sweep 1 computes H_p = A_p^{l-1} W for every partition into the
+            // whole-graph buffer, sweep 2 gathers and aggregates rows of H.  No partition needs
+            // another partition's block of A^{l-1}, so nothing is cached for the gather: an input
+            // block comes from a whole array if the pool already holds one, else through a transfer
+            // buffer (twice for GraphSAGE, whose self term reads it again in sweep 2).
+            Resident* in = nullptr;
+            Resident* out = nullptr;
+            if ((st = ensure_array(c, E, keep[0], act_slot_bytes(l - 1), act_row_bytes(l - 1), act_host(l - 1), false,
+                                   keep, 2, nullptr, 0, true, &in)) != GNN_OK) return st;
+            if ((st = ensure_array(c, E, keep[1], act_slot_bytes(l), act_row_bytes(l), act_host(l), false, keep,
+                                   2, nullptr, 0, true, &out)) != GNN_OK) return st;
+            const int64_t in_row = act_row_bytes(l - 1), out_row = (int64_t)dout * c->act_es(l);
+            const bool sage = c->model == GNN_SAGE_MEAN;
+            auto want_input = [&](int32_t t, int i, BlockReq& r) -> gnn_status {
+                if (i != 2) return GNN_OK;
+                const int32_t p = M.sched[(size_t)t];
+                if (in) return from_array(in, p, r);
+                const int64_t r0 = M.off[(size_t)p], np = M.off[(size_t)p + 1] - r0;
+                r.host = act_host(l - 1) + r0 * in_row;
+                r.bytes = np * in_row;
+                return GNN_OK;
+            };
+            st = xf_sweep(want_input, [&](int32_t t, const BlockReq* b) -> gnn_status {
+                xf_transform_fwd(c, l, M.sched[(size_t)t], b[2].dev, s);
+                return GNN_OK;
+            });
+            if (st != GNN_OK) return st;
+            auto want_self = [&](int32_t t, int i, BlockReq& r) -> gnn_status {
+                return sage ? want_input(t, i, r) : GNN_OK;
+            };
+            st = xf_sweep(want_self, [&](int32_t t, const BlockReq* b) -> gnn_status {
+                const int32_t p = M.sched[(size_t)t];
+                const int64_t r0 = M.off[(size_t)p], np = M.off[(size_t)p + 1] - r0;
+                const int64_t b0 = M.boff[(size_t)p], nb = M.boff[(size_t)p + 1] - b0;
+                {
+                    Timed timed(c, s, GNN_K_GATHER);
+                    launch_gather_rows(c->hbuf, c->D.bnd + b0, c->staging, nb, (int64_t)c->padded(l) * c->es(), s);
+                }
+                char* host_rows = c->act[(size_t)l - 1] + r0 * out_row;
+                gnn_status r_st;
+                if (out) {
+                    xf_aggregate_fwd(c, l, p, b[2].dev, out->bc.ptr(p), s);
+                    return produced(out, p, host_rows, np * out_row);
+                }
+                const int ob = t & 1;
+                if ((r_st = wait_out_free(ob)) != GNN_OK) return r_st;
+                xf_aggregate_fwd(c, l, p, b[2].dev, E.outbuf(ob), s);
+                return store_out(ob, host_rows, np * out_row);
+            });
+            if (st != GNN_OK) return st;
+            if ((st = end_of_layer()) != GNN_OK) return st;
+            continue;
+        }
         // the layer's input as a whole array if it fits, and then its output as well; an input
         // that does not fit is streamed through a block cache over the whole pool
         Resident* in = nullptr;
@@ -769,13 +905,6 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
     float* scal = (float*)(c->scratch + c->ws.scalars);
     unsigned long long* count_dev = (unsigned long long*)(scal + 16);
     float* losspart = (float*)(c->scratch + c->ws.losspart);
-    // Loads rows of a host array into transfer buffer `dst` on the load stream.
-    auto load_in = [&](char* dst, const char* src, int64_t bytes, int ib, bool first) -> gnn_status {
-        if (first && E.has_in_released[ib]) GNN_HIP(hipStreamWaitEvent(E.h2d, E.in_released[ib], 0));
-        if (bytes > 0) GNN_HIP(hipMemcpyAsync(dst, src, (size_t)bytes, hipMemcpyHostToDevice, E.h2d));
-        E.h2d_bytes += bytes;
-        return GNN_OK;
-    };
     {
         const int32_t C = c->dims[(size_t)L];
         const Key keep[3] = {{ARR_ACT, L}, {ARR_GRAD, L}, {ARR_ACT, L - 1}};
@@ -832,6 +961,75 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
         const Key keep[4] = {{ARR_GRAD, l - 1}, {ARR_ACT, l - 1}, {ARR_GRAD, l}, {ARR_ACT, l}};
         const int64_t a_slot = act_slot_bytes(l - 1), g_slot = grad_slot_bytes(l - 1);
         const int64_t a_blk = round256(a_slot), g_blk = round256(g_slot);      // slots of a block cache
+        if (c->transform_first(l)) {
+            // Transform-first layer: sweep 1 scatter-accumulates S_p^T dY_p into the whole-graph
+            // buffer grad H (so no block of grad A^{l-1} is ever cycled through a cache), sweep 2
+            // produces grad A_p^{l-1} block by block, each written once.  Input blocks come from
+            // whole arrays still in the pool, else through transfer buffers.
+            Resident* gin = find_array(E, keep[2]);
+            Resident* ain = l < L ? find_array(E, keep[3]) : nullptr;
+            Resident* srcarr = find_array(E, keep[1]);
+            Resident* gout = nullptr;
+            if (need_prev && (st = ensure_array(c, E, keep[0], g_slot, (int64_t)din * 4, (char*)c->gact[(size_t)l - 2],
+                                                false, keep, 4, nullptr, 0, true, &gout)) != GNN_OK) return st;
+            const bool sage = c->model == GNN_SAGE_MEAN;
+            const int64_t in_row = act_row_bytes(l - 1);
+            auto block = [&](int32_t t, int i, BlockReq& r) -> gnn_status {
+                const int32_t p = M.sched[(size_t)t];
+                const int64_t r0 = M.off[(size_t)p], np = M.off[(size_t)p + 1] - r0;
+                Resident* arr = i == 0 ? gin : i == 1 ? ain : srcarr;
+                if (arr && (i == 2 || arr->bc.holds(p))) {
+                    if (i == 2) return from_array(arr, p, r);
+                    r.dev = arr->bc.ptr(p);
+                    return GNN_OK;
+                }
+                if (i == 0) { r.host = (const char*)(c->gact[(size_t)l - 1] + r0 * dout); r.bytes = np * dout * 4; }
+                else if (i == 1) { r.host = c->act[(size_t)l - 1] + r0 * act_row; r.bytes = np * act_row; }
+                else { r.host = act_host(l - 1) + r0 * in_row; r.bytes = np * in_row; }
+                return GNN_OK;
+            };
+            xf_begin_bwd(c, l, s);
+            st = xf_sweep([&](int32_t t, int i, BlockReq& r) -> gnn_status {
+                              if (i == 1 && l == L) return GNN_OK;        // the output layer has no activation
+                              if (i == 2 && !sage) return GNN_OK;         // A^{l-1} feeds the self-weight gradient only
+                              return block(t, i, r);
+                          },
+                          [&](int32_t t, const BlockReq* b) -> gnn_status {
+                              xf_aggregate_bwd(c, l, M.sched[(size_t)t], b[2].dev, (const float*)b[0].dev, b[1].dev, nullptr, s);
+                              return GNN_OK;
+                          });
+            if (st != GNN_OK) return st;
+            st = xf_sweep([&](int32_t t, int i, BlockReq& r) -> gnn_status {
+                              if (i == 1) return GNN_OK;
+                              if (i == 0 && !(sage && l == L && need_prev)) return GNN_OK;   // dY of a GraphSAGE output layer
+                              return block(t, i, r);
+                          },
+                          [&](int32_t t, const BlockReq* b) -> gnn_status {
+                              const int32_t p = M.sched[(size_t)t];
+                              const int64_t r0 = M.off[(size_t)p], np = M.off[(size_t)p + 1] - r0;
+                              if (!need_prev) {
+                                  xf_transform_bwd(c, l, p, b[2].dev, (const float*)b[0].dev, nullptr, s);
+                                  return GNN_OK;
+                              }
+                              char* host_rows = (char*)(c->gact[(size_t)l - 2] + r0 * din);
+                              gnn_status r_st;
+                              if (gout) {
+                                  xf_transform_bwd(c, l, p, b[2].dev, (const float*)b[0].dev, (float*)gout->bc.ptr(p), s);
+                                  return produced(gout, p, host_rows, np * din * 4);
+                              }
+                              const int ob = t & 1;
+                              if ((r_st = wait_out_free(ob)) != GNN_OK) return r_st;
+                              xf_transform_bwd(c, l, p, b[2].dev, (const float*)b[0].dev, (float*)E.outbuf(ob), s);
+                              return store_out(ob, host_rows, np * din * 4);
+                          });
+            if (st != GNN_OK) return st;
+            if ((st = end_of_layer()) != GNN_OK) return st;
+            if (Resident* r = find_array(E, keep[2]))
+                if ((st = release_array(c, E, r)) != GNN_OK) return st;
+            if (Resident* r = find_array(E, keep[3]))
+                if ((st = release_array(c, E, r)) != GNN_OK) return st;
+            continue;
+        }
         // Whole arrays where they fit: the gradient being accumulated first (a block of it that is
         // evicted costs a write-back and a reload), then the gather source; the partition's own
         // gradient and activation blocks are taken from arrays that are still in the pool.

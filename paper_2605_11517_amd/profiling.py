@@ -3,6 +3,16 @@
     python -m paper_2605_11517_amd.profiling stats  <dir-with-*_kernel_stats.csv>  <out.md> "<command>"
     python -m paper_2605_11517_amd.profiling pmc    <fetch-dir> <write-dir> <out.md> "<command>"
 
+    python -m paper_2605_11517_amd.profiling mfma   <pmc-dir> <out.md> "<command>"
+
+``mfma`` expects one counter run with ``--pmc SQ_BUSY_CU_CYCLES SQ_VALU_MFMA_BUSY_CYCLES
+--kernel-trace`` and reports, per contraction kernel, the clock the compute units ran at
+(busy cycles of the 256 CUs over the kernel's duration) and the share of those cycles in which
+a SIMD's matrix pipe was busy (four SIMDs per CU).
+
+An optional last argument of every mode is the commit the run was taken at; it is written into
+the summary ("Taken at commit ...").
+
 ``pmc`` expects two counter runs of the same command (``--pmc FETCH_SIZE`` and
 ``--pmc WRITE_SIZE``, each with ``--kernel-trace``) that include one plain 1 GiB device copy
 (``bench.py --copy-calibration``).  The counters are reported in KiB per dispatch; each is
@@ -35,11 +45,13 @@ def _one(pattern):
     return hits[0]
 
 
-def summarize_stats(src_dir: str, out_path: str, command: str) -> None:
+def summarize_stats(src_dir: str, out_path: str, command: str, commit: str = "") -> None:
     rows = list(csv.DictReader(open(_one(os.path.join(src_dir, "*kernel_stats.csv")))))
     total = sum(float(r["TotalDurationNs"]) for r in rows)
-    lines = ["# rocprofv3 --kernel-trace --stats", "", "Command:", "", "    " + command, "",
-             "| kernel | calls | total ms | avg us | % |", "|---|---:|---:|---:|---:|"]
+    lines = ["# rocprofv3 --kernel-trace --stats", "", "Command:", "", "    " + command, ""]
+    if commit:
+        lines += ["Taken at commit %s." % commit, ""]
+    lines += ["| kernel | calls | total ms | avg us | % |", "|---|---:|---:|---:|---:|"]
     for r in rows:
         t = float(r["TotalDurationNs"])
         if t / total < 0.001:
@@ -63,7 +75,7 @@ def _per_kernel(path, counter):
     return out
 
 
-def summarize_pmc(fetch_dir: str, write_dir: str, out_path: str, command: str) -> None:
+def summarize_pmc(fetch_dir: str, write_dir: str, out_path: str, command: str, commit: str = "") -> None:
     fetch = _per_kernel(_one(os.path.join(fetch_dir, "*counter_collection.csv")), "FETCH_SIZE")
     write = _per_kernel(_one(os.path.join(write_dir, "*counter_collection.csv")), "WRITE_SIZE")
 
@@ -77,7 +89,7 @@ def summarize_pmc(fetch_dir: str, write_dir: str, out_path: str, command: str) -
 
     fs, ws = copy_scale(fetch), copy_scale(write)
     lines = ["# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs)", "", "Command (run once per counter):",
-             "", "    " + command, "",
+             "", "    " + command, ""] + (["Taken at commit %s." % commit, ""] if commit else []) + [
              "Scale factors from the 1 GiB calibration copy: FETCH_SIZE x %.3f, WRITE_SIZE x %.3f "
              "(counter KiB -> real KiB)." % (fs, ws), "",
              "| kernel | launches | read GB | written GB | GB per launch | ms per launch | GB/s |",
@@ -97,6 +109,40 @@ def summarize_pmc(fetch_dir: str, write_dir: str, out_path: str, command: str) -
             name, e["launches"], rd, wr, (rd + wr) / e["launches"], ms / e["launches"],
             (rd + wr) / (ms / 1e3) if ms > 0 else 0.0))
     lines += ["", "TRAFFIC_JSON: " + json.dumps(table)]
+    open(out_path, "w").write("\n".join(lines) + "\n")
+
+
+def summarize_mfma(src_dir: str, out_path: str, command: str, commit: str = "") -> None:
+    path = _one(os.path.join(src_dir, "*counter_collection.csv"))
+    per = collections.OrderedDict()
+    seen = set()
+    for r in csv.DictReader(open(path)):
+        name = short_name(r["Kernel_Name"])
+        e = per.setdefault(name, {"busy": 0.0, "mfma": 0.0, "launches": 0, "ns": 0})
+        if r["Counter_Name"] == "SQ_BUSY_CU_CYCLES":
+            e["busy"] += float(r["Counter_Value"])
+        elif r["Counter_Name"] == "SQ_VALU_MFMA_BUSY_CYCLES":
+            e["mfma"] += float(r["Counter_Value"])
+        key = (r["Dispatch_Id"], name)
+        if key not in seen:
+            seen.add(key)
+            e["launches"] += 1
+            e["ns"] += int(r["End_Timestamp"]) - int(r["Start_Timestamp"])
+    lines = ["# rocprofv3 --pmc SQ_BUSY_CU_CYCLES SQ_VALU_MFMA_BUSY_CYCLES (matrix-pipe utilisation)", "",
+             "Command:", "", "    " + command, ""]
+    if commit:
+        lines += ["Taken at commit %s." % commit, ""]
+    lines += ["clock = SQ_BUSY_CU_CYCLES / (256 CUs x duration); pipe busy = SQ_VALU_MFMA_BUSY_CYCLES / "
+              "(4 SIMDs x SQ_BUSY_CU_CYCLES); vs 2.4 GHz = SQ_VALU_MFMA_BUSY_CYCLES / (1024 SIMDs x duration x 2.4 GHz), "
+              "the share of the published peak's issue slots that held a matrix instruction.", "",
+             "| kernel | launches | avg us | clock GHz | MFMA pipe busy | vs 2.4 GHz |", "|---|---:|---:|---:|---:|---:|"]
+    for name, e in per.items():
+        if e["mfma"] <= 0 or e["ns"] <= 0 or e["busy"] <= 0:
+            continue
+        dur = e["ns"] * 1e-9
+        lines.append("| %s | %d | %.1f | %.2f | %.3f | %.3f |" % (
+            name, e["launches"], e["ns"] / e["launches"] / 1e3, e["busy"] / 256.0 / dur / 1e9,
+            e["mfma"] / (4.0 * e["busy"]), e["mfma"] / (1024.0 * dur * 2.4e9)))
     open(out_path, "w").write("\n".join(lines) + "\n")
 
 
@@ -125,8 +171,10 @@ def read_traffic(path: str):
 
 if __name__ == "__main__":
     if len(sys.argv) >= 5 and sys.argv[1] == "stats":
-        summarize_stats(sys.argv[2], sys.argv[3], sys.argv[4])
+        summarize_stats(sys.argv[2], sys.argv[3], sys.argv[4], *sys.argv[5:6])
+    elif len(sys.argv) >= 5 and sys.argv[1] == "mfma":
+        summarize_mfma(sys.argv[2], sys.argv[3], sys.argv[4], *sys.argv[5:6])
     elif len(sys.argv) >= 6 and sys.argv[1] == "pmc":
-        summarize_pmc(sys.argv[2], sys.argv[3], sys.argv[4], sys.argv[5])
+        summarize_pmc(sys.argv[2], sys.argv[3], sys.argv[4], sys.argv[5], *sys.argv[6:7])
     else:
         sys.exit(__doc__)

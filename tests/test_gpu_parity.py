@@ -334,6 +334,60 @@ def test_streaming_schedule_is_bit_identical_to_resident(case):
     assert e.value.status == 5
 
 
+@pytest.mark.parametrize("name,dims,extra", [
+    ("mini_sage", (100, 256, 256, 47), 1.0),            # hidden GraphSAGE layer keeps its dY rows; padded 48-wide output
+    ("mini_sage", (100, 256, 256, 47), 3.0),
+    ("mini_gcn_directed", (128, 128, 128, 172), 1.0),
+    ("tiny", (64, 64, 16), 2.0),
+    ("mini_sage", (64, 32, 32, 8), 1.0),                # every layer transforms first
+])
+def test_streaming_transform_first_layers_are_bit_identical_to_resident(name, dims, extra):
+    """Layer order by rows moved in the streaming schedule: the whole-graph buffers of the
+    transform-first layers come out of the HBM budget, the rest is the block cache (`extra` times
+    its minimum).  Same bits as the resident schedule with the same order; with a budget that
+    cannot hold those buffers the schedule falls back to the paper's order for every layer."""
+    say("case streaming transform-first %s %s x%g" % (name, dims, extra))
+    from paper_2605_11517_amd import Session
+    cfg, rowptr, colidx = make_config(name)
+    cfg = dict(cfg, dims=dims)
+    n = cfg["n"]
+    X, y, m, w = make_inputs(cfg, n)
+    res = Session(cfg["model"], dims, rowptr, colidx, cfg["k"], cfg["part"], cfg["seed"], X, w, y, m,
+                  layer_order="auto")
+    L = len(dims) - 1
+    order = [res.ctx.layer_is_transform_first(l) for l in range(1, L + 1)]
+    assert any(order)
+    loss_res = res.epoch()
+    r_res = res.results()
+    st = res.ctx.get_stats()
+    rnd = lambda b: (b + 255) // 256 * 256
+    pad = lambda d: (d + 3) // 4 * 4
+    hp = max(pad(dims[l]) for l in range(1, L + 1) if order[l - 1])
+    dyw = max([pad(dims[l]) for l in range(2, L) if order[l - 1] and cfg["model"] == "sage"] or [0])
+    xf_bytes = rnd(n * hp * 4) + rnd(n * dyw * 4)
+    minimum = 4 * rnd(max(1, st["max_own"]) * max(dims) * 4)
+    s = Session(cfg["model"], dims, rowptr, colidx, cfg["k"], cfg["part"], cfg["seed"], X, w, y, m,
+                layer_order="auto", hbm_budget_bytes=int(xf_bytes + minimum * extra))
+    assert [s.ctx.layer_is_transform_first(l) for l in range(1, L + 1)] == order
+    for rep in range(2):
+        assert s.epoch() == loss_res
+        got = s.results()
+        for key in ("act", "gact", "gW", "gWs", "gb"):
+            for l, (a, b) in enumerate(zip(got[key], r_res[key])):
+                if a is None:
+                    assert b is None
+                    continue
+                assert np.array_equal(a, b), (rep, key, l)
+    ref = og.epoch(cfg["model"], rowptr, colidx, dims, X, w, y, m)
+    compare(got, ref, cfg["model"], tag="streaming transform-first " + name)
+    # one byte short of the buffers plus the smallest cache: every layer keeps the paper's order
+    s2 = Session(cfg["model"], dims, rowptr, colidx, cfg["k"], cfg["part"], cfg["seed"], X, w, y, m,
+                 layer_order="auto", hbm_budget_bytes=int(xf_bytes + minimum - 256))
+    assert not any(s2.ctx.layer_is_transform_first(l) for l in range(1, L + 1))
+    s2.epoch()
+    compare(s2.results(), ref, cfg["model"], tag="streaming fallback " + name)
+
+
 def test_streaming_and_resident_epochs_on_a_created_stream():
     """The caller's compute stream need not be the null stream: on a stream created by the caller
     (which orders itself against nothing implicitly) every schedule gives the bits it gives on
