@@ -84,11 +84,22 @@ def algorithmic_bytes(stats, dims, model, n_parts, es=4, fused_scatter=False, xf
     return out
 
 
-def gemm_flops(stats, dims, model):
+def fused_layers(dims, xf, dtype):
+    """Layers (0-based) whose forward contraction runs inside the aggregation kernel (the
+    aggregated tile stays in LDS); mirrors spmm_gemm_fused_ok() of the library."""
+    if dtype != "f32" or os.environ.get("GNNMI_FUSE_AGG", "1")[:1] == "0":
+        return []
+    return [l for l in range(len(dims) - 1)
+            if not xf[l] and dims[l] % 4 == 0 and 32 < dims[l] <= 128 and dims[l + 1] <= 256]
+
+
+def gemm_flops(stats, dims, model, fused=()):
+    """Flops of the contractions that run as kernels of their own, by class (the forward
+    contraction of a fused layer is part of the aggregation kernel's time, so it is left out)."""
     n = stats["n"]
     L = len(dims) - 1
     mult = 2 if model == "sage" else 1
-    fwd = sum(2 * n * dims[l] * dims[l + 1] * mult for l in range(L))
+    fwd = sum(2 * n * dims[l] * dims[l + 1] * mult for l in range(L) if l not in fused)
     dw = fwd
     dz = sum(2 * n * dims[l] * dims[l + 1] * mult for l in range(1, L))
     return {"gemm_fwd": fwd, "gemm_dw": dw, "gemm_dz": dz}
@@ -184,8 +195,9 @@ def run_workload(name, args, steps, warmup, want_cpu):
         cfg["part"] = args.partitioner
     budget = int(args.hbm_budget_gb * 2 ** 30)
     if name == "beyond" and not budget:
-        # the beyond-HBM recipe always streams: a block cache of a fifth of activations + gradients
-        budget = n * (sum(dims) + sum(dims[1:])) * 4 // 5
+        # the beyond-HBM recipe always streams, with HBM in the proportion the full recipe would
+        # find on this device: 288 GB for 512 GB of activations and gradients
+        budget = int(n * (sum(dims) + sum(dims[1:])) * 4 * 0.56)
     s = Session(model, dims, rowptr, colidx, cfg["k"], cfg["part"], cfg["seed"], X, w, y, m,
                 dtype=cfg["dtype"], hbm_budget_bytes=budget,
                 layer_order=args.layer_order, progress=lambda msg: log("  " + msg))
@@ -303,7 +315,9 @@ def run_workload(name, args, steps, warmup, want_cpu):
     if prof:
         ab = algorithmic_bytes(stats, dims, model, stats["k"], es,
                                fused_scatter=prof.get("scatter", (0, 0))[1] == 0, xf=xf)
-        fl = gemm_flops(stats, dims, model)
+        fused = fused_layers(dims, xf, cfg["dtype"]) if model != "gat" else []
+        fl = gemm_flops(stats, dims, model, fused)
+        out["config"]["forward_fused_with_aggregation"] = [l + 1 for l in fused]
         # per kernel class, from the one epoch run after the timed region with every class bracketed,
         # on one stream
         classes = {}

@@ -180,9 +180,9 @@ void compute_workspace(gnn_ctx* c)
         int64_t dyw = 0;
         for (int32_t l = 2; l < L; ++l)
             if (c->transform_first(l)) dyw = std::max<int64_t>(dyw, c->padded(l));
-        if (dyw > 0) {
+        if (dyw > 0 && !c->streaming()) {
             w.dyall_floats = M.n * dyw;
-            if (!c->streaming()) w.dyall = take(M.n * dyw);
+            w.dyall = take(M.n * dyw);
         }
     }
     if (c->model == GNN_GAT) {
@@ -297,6 +297,39 @@ void compute_fwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, char*
     const HostMeta& M = c->M;
     const int64_t np = M.off[(size_t)p + 1] - M.off[(size_t)p];
     const int32_t din = c->dims[(size_t)layer - 1], dout = c->dims[(size_t)layer];
+    if (!c->bf16()) {
+        // aggregate and transform in one kernel, the aggregated rows staying in LDS
+        const SpmmItems items = plan_items(M.plan_fwd, c->D.fwd, p);
+        if (spmm_gemm_fused_ok(din, dout, items)) {
+            const int64_t r0 = M.off[(size_t)p];
+            const bool sage = c->model == GNN_SAGE_MEAN;
+            const float* rscale = c->D.rscale ? c->D.rscale + r0 : nullptr;
+            float* zlong = (float*)(c->scratch + c->z_off());
+            if (items.nsegs > 0) {
+                Timed t(c, s, GNN_K_SPMM_REDUCE);
+                launch_spmm_long_rows(c->D.rp + r0, c->D.lcol, c->D.ew, rscale, (const float*)in_own, np,
+                                      (const float*)c->staging, din, items, (float*)(c->scratch + c->ws.segpart), zlong, s);
+            }
+            {
+                Timed t(c, s, GNN_K_SPMM);
+                launch_spmm_gemm_fused(c->D.rp + r0, c->D.lcol, c->D.ew, rscale,
+                                       (const float*)in_own, np, (const float*)c->staging, din, items, zlong,
+                                       sage ? (const float*)in_own : nullptr, (const float*)c->w[(size_t)3 * (layer - 1)],
+                                       sage ? (const float*)c->w[(size_t)3 * (layer - 1) + 1] : nullptr,
+                                       c->has_bias ? (const float*)c->w[(size_t)3 * (layer - 1) + 2] : nullptr,
+                                       layer < c->L ? 1 : 0, (float*)out_own, dout, s);
+            }
+            if (c->fwd_side)      // this region of Z is free again once the kernels above have run
+                if (hipEventRecord(c->side_events[c->side_events.size() - 2 + (size_t)c->z_slot], s) != hipSuccess)
+                    c->deferred = hipErrorUnknown;
+            if (c->dropout_p > 0.f && layer < c->L) {
+                const uint64_t key = splitmix64(c->dropout_seed ^ splitmix64((uint64_t)(64 * c->dropout_epoch + layer)));
+                const uint32_t threshold = (uint32_t)std::floor((double)c->dropout_p * 4294967296.0);
+                launch_dropout(out_own, 0, c->D.order + r0, np, dout, key, threshold, 1.f / (1.f - c->dropout_p), s);
+            }
+            return;
+        }
+    }
     run_spmm_fwd(c, layer, p, in_own, s);
     if (c->fwd_side) {
         // gnn_epoch, resident: the contraction (and the dropout behind it) goes to the side stream
@@ -644,7 +677,7 @@ void xf_aggregate_bwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own_c
             launch_gemm_tn(in_own, din, dYp, dp, c->gw[(size_t)3 * (layer - 1) + 1], dout, din, dout, np,
                            (float*)(c->scratch + c->ws.partial), s);
         }
-        if (layer >= 2 && layer < L && !keep) {
+        if (layer >= 2 && layer < L && !keep && gprev_own) {
             // self term: grad A^{l-1}_own = dY W_s^T (the first thing written to these rows),
             // contracted over the padded width.  (Not reached while the workspace keeps dY of every
             // partition: then the second sweep takes both terms of grad A^{l-1} in one contraction,
@@ -704,9 +737,11 @@ void xf_transform_fwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, 
 
 // Transform-first layer, second sweep of the backward pass, once grad H is complete:
 // grad W += A_p^{l-1 T} grad H_p, grad A_p^{l-1} = grad H_p W^T (+ dY_p W_s^T).  g_own = grad A_p^l
-// (read only by a GraphSAGE output layer, whose dY is grad A^L itself).
+// (read by a GraphSAGE output layer, whose dY is grad A^L itself).  act_own = A_p^l: given for a
+// hidden GraphSAGE layer when the first sweep kept no dY rows (streaming schedule); dY_p is then
+// taken again from g_own and act_own, the same values, and enters the same contraction.
 void xf_transform_bwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own_c, const float* g_own,
-                      float* gprev_own, hipStream_t s)
+                      const char* act_own, float* gprev_own, hipStream_t s)
 {
     const HostMeta& M = c->M;
     const int64_t r0 = M.off[(size_t)p], np = M.off[(size_t)p + 1] - r0;
@@ -739,11 +774,31 @@ void xf_transform_bwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own_c
         launch_gemm_tn(in_own, din, gH, dp, c->gw[(size_t)3 * (layer - 1)], dout, din, dout, np,
                        (float*)(c->scratch + (c->on_side ? c->ws.partial2 : c->ws.partial)), s);
     }
-    const bool kept = c->model == GNN_SAGE_MEAN && layer >= 2 && layer < c->L && c->dyall_buf;
+    const float* dYk = nullptr;          // padded dY_p of a hidden GraphSAGE layer
+    if (c->model == GNN_SAGE_MEAN && layer >= 2 && layer < c->L) {
+        if (c->dyall_buf) {
+            dYk = c->dyall_buf + r0 * dp;
+        } else if (act_own) {
+            float* dyb = (float*)(c->scratch + c->ws.dy);
+            {
+                Timed t(c, s, GNN_K_ACT_BWD);
+                launch_act_bwd(g_own, (const float*)act_own, dyb, np, dout, nullptr, (float*)(c->scratch + c->ws.colpart),
+                               c->dropout_p > 0.f ? 1.f / (1.f - c->dropout_p) : 1.f, s);
+            }
+            dYk = dyb;
+            if (dp != dout) {
+                Timed t(c, s, GNN_K_OTHER);
+                float* pad = (float*)(c->scratch + c->ws.dz);
+                launch_pad_rows(pad, dyb, np, dout, dp, s);
+                dYk = pad;
+            }
+        }
+    }
+    const bool kept = dYk != nullptr;
     if (layer >= 2 && (layer == c->L || kept) && c->model == GNN_SAGE_MEAN) {
         // grad A^{l-1}_own = grad H_p W^T + dY_p W_s^T in one pass over the result: the output
         // layer's dY_p is grad A^L_p, a hidden layer's padded dY_p was kept by the first sweep
-        const float* dY = kept ? c->dyall_buf + r0 * dp : g_own;
+        const float* dY = kept ? dYk : g_own;
         if (!kept && dp != dout) {
             Timed t(c, s, GNN_K_OTHER);
             float* pad = (float*)(c->scratch + c->ws.dz);
@@ -1121,7 +1176,7 @@ gnn_status gnn_layer_transform_bwd(gnn_ctx* c, int32_t layer, int32_t p, void* s
     } else {
         const int64_t r0 = M.off[(size_t)p];
         xf_transform_bwd(c, layer, p, c->layer_input(layer, r0),
-                         c->gact[(size_t)layer - 1] + r0 * c->dims[(size_t)layer],
+                         c->gact[(size_t)layer - 1] + r0 * c->dims[(size_t)layer], nullptr,
                          layer >= 2 ? c->gact[(size_t)layer - 2] + r0 * c->dims[(size_t)layer - 1] : nullptr, s);
     }
     c->xf_bwd_done[(size_t)(layer - 1) * (size_t)M.k + (size_t)p] = 1;

@@ -127,7 +127,8 @@ struct gnn_ctx {
         for (int32_t l = 1; l <= L; ++l)
             if (wants_transform_first(l)) {
                 hp = std::max<int64_t>(hp, padded(l));
-                if (model == GNN_SAGE_MEAN && l >= 2 && l < L) dyw = std::max<int64_t>(dyw, padded(l));
+                // (the streaming schedule keeps no dY rows: its second sweep takes them again)
+                if (model == GNN_SAGE_MEAN && l >= 2 && l < L && !streaming()) dyw = std::max<int64_t>(dyw, padded(l));
             }
         return (n * hp * 4 + 255) / 256 * 256 + (n * dyw * 4 + 255) / 256 * 256;
     }
@@ -247,7 +248,7 @@ void xf_begin_bwd(gnn_ctx* c, int32_t layer, hipStream_t s);
 void xf_aggregate_bwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, const float* g_own,
                       const char* act_own, float* gprev_own, hipStream_t s);
 void xf_transform_bwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, const float* g_own,
-                      float* gprev_own, hipStream_t s);
+                      const char* act_own, float* gprev_own, hipStream_t s);
 
 void zero_weight_grads(gnn_ctx* c, hipStream_t s);
 SpmmItems plan_items(const HostMeta::Plan& H, const DevMeta::Plan& P, int32_t p);

@@ -479,6 +479,209 @@ __global__ __launch_bounds__(kBlock) void k_spmm_slots(const SpmmArgs g, int32_t
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Aggregation fused with the transform (aggregate-first layers, fp32, d_in <= 128, d_out <= 256).
+//
+// A workgroup owns 64 destination rows.  Phase 1: its four wavefronts aggregate those rows as
+// the slot kernel above does (G lanes per row, rows taken from the degree-sorted list so that
+// the slots of a wavefront finish together) and leave the sums Z in LDS instead of in memory;
+// rows that were cut into segments arrive through `zlong` (their sums were combined by the
+// long-row kernel) and are copied.  For GraphSAGE the rows' own input rows are staged beside
+// them.  Phase 2: Y = act(Z W (+ X W_s) + b) on the fp32 matrix cores straight from that tile
+// (v_mfma_f32_32x32x2f32: A fragments from LDS, B fragments - rows of W, shared by every
+// workgroup and resident in L2 - from memory), stored to the rows' places in the output.
+// Z is neither written nor read back, and the contraction runs in the shadow of the other
+// workgroups' row fetches.
+// ---------------------------------------------------------------------------------------------
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+struct FusedArgs {
+    SpmmArgs sp;            // operator rows and sources; sp.out is unused
+    const float* zlong;     // [n_p, d_in]: valid in the rows listed in sp.it.long_row
+    const float* xself;     // own input rows [n_p, d_in] (GraphSAGE), else null
+    const float* w;         // [d_in, d_out]
+    const float* ws;        // [d_in, d_out] or null
+    const float* bias;      // [d_out] or null
+    float* y;               // [n_p, d_out]
+    int32_t dout, relu;
+    int32_t kp;             // LDS row stride in floats (odd)
+};
+
+template <int G>
+__global__ __launch_bounds__(kBlock) void k_agg_gemm(const FusedArgs g)
+{
+    constexpr int TM = 64;                      // rows per workgroup
+    constexpr int S = kWave / G;                // row slots per wavefront
+    constexpr int RPW = TM / (kBlock / kWave);  // rows per wavefront: 16
+    constexpr int UNROLL = 8;
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    float* Zs = lds;                            // [TM][kp]
+    float* Xs = lds + TM * g.kp;                // [TM][kp], GraphSAGE only
+    const SpmmArgs& sp = g.sp;
+    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+    const int slot = lane / G, gl = lane % G;
+    const int32_t din = sp.d;
+    const int64_t nrows = sp.it.nshort + sp.it.nlong;
+    const int64_t tile0 = (int64_t)blockIdx.x * TM;
+    const float* a_rows = static_cast<const float*>(sp.a_rows);
+    const float* b_rows = static_cast<const float*>(sp.b_rows);
+    const int coff = gl * 4;
+    const bool live = coff < din;
+    const int cload = live ? coff : 0;
+
+    // ---- phase 1: sums of this wavefront's 16 rows, S at a time
+    for (int r0 = 0; r0 < RPW; r0 += S) {
+        const int tr = wave * RPW + r0 + slot;          // row of the tile
+        const int64_t li = tile0 + tr;                  // position in the sorted list
+        int32_t row = -1;
+        int64_t e_begin = 0;
+        int32_t len = 0;
+        bool is_long = false;
+        if (li < sp.it.nshort) {
+            row = sp.it.rows_sorted[li];
+            e_begin = sp.rp[row];
+            len = (int32_t)(sp.rp[row + 1] - e_begin);
+        } else if (li < nrows) {
+            row = sp.it.long_row[li - sp.it.nshort];
+            is_long = true;
+        }
+        int32_t maxlen = len;
+        int lead = slot;
+#pragma unroll
+        for (int m = G; m < kWave; m <<= 1) {
+            const int32_t ol = __shfl_xor(maxlen, m, kWave);
+            const int os = __shfl_xor(lead, m, kWave);
+            if (ol > maxlen || (ol == maxlen && os < lead)) { maxlen = ol; lead = os; }
+        }
+        float acc[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int32_t e0 = 0; e0 < maxlen; e0 += G) {
+            int32_t my_c = 0;
+            float my_w = 0.f;
+            if (e0 + gl < len) {
+                my_c = sp.col[e_begin + e0 + gl];
+                my_w = sp.w ? sp.w[e_begin + e0 + gl] : 1.f;
+            }
+            const int cnt = len - e0;
+            const int lead_cnt = maxlen - e0 < G ? maxlen - e0 : G;
+#pragma unroll
+            for (int j0 = 0; j0 < G; j0 += UNROLL) {
+                if (j0 >= lead_cnt) break;
+                float4 x[UNROLL];
+                float ww[UNROLL];
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) {
+                    const int j = j0 + u;
+                    const bool on = j < cnt;
+                    const int src_lane = on ? slot * G + j : lead * G + (j < lead_cnt ? j : lead_cnt - 1);
+                    const int32_t c = __shfl(my_c, src_lane, kWave);
+                    const float wt = __shfl(my_w, src_lane, kWave);
+                    ww[u] = on ? wt : 0.f;
+                    const float* src = (c < sp.n_a) ? a_rows + (int64_t)c * sp.ld : b_rows + ((int64_t)c - sp.n_a) * sp.ld;
+                    x[u] = *reinterpret_cast<const float4*>(src + cload);
+                }
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) {
+                    const bool on = (j0 + u) < cnt;
+                    acc[0] += on ? ww[u] * x[u].x : 0.f;
+                    acc[1] += on ? ww[u] * x[u].y : 0.f;
+                    acc[2] += on ? ww[u] * x[u].z : 0.f;
+                    acc[3] += on ? ww[u] * x[u].w : 0.f;
+                }
+            }
+        }
+        if (live) {
+            float z[4] = {0.f, 0.f, 0.f, 0.f};
+            if (is_long) {
+                const float4 v = *reinterpret_cast<const float4*>(g.zlong + (int64_t)row * din + coff);
+                z[0] = v.x; z[1] = v.y; z[2] = v.z; z[3] = v.w;
+            } else if (row >= 0) {
+                const float sc = sp.rowscale ? sp.rowscale[row] : 1.f;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) z[i] = sc * acc[i];
+            }
+            float* zr = Zs + tr * g.kp + coff;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) zr[i] = z[i];
+            if (g.xself) {
+                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (row >= 0) v = *reinterpret_cast<const float4*>(g.xself + (int64_t)row * din + coff);
+                float* xr = Xs + tr * g.kp + coff;
+                xr[0] = v.x; xr[1] = v.y; xr[2] = v.z; xr[3] = v.w;
+            }
+        }
+    }
+    // the k loop below runs to an even bound: one more column when d_in is odd (never: d_in % 4 == 0)
+    __syncthreads();
+
+    // ---- phase 2: Y tile = Zs W (+ Xs W_s); wavefront w owns the 32-column tiles w, w + 4, ...
+    const int half = lane >> 5, xl = lane & 31;
+    const int nseg = g.xself ? 2 : 1;
+    floatx16 acc2[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc2[i][j][r] = 0.f;
+    const int32_t col0 = 32 * wave + xl, col1 = 32 * (wave + 4) + xl;
+    const bool c0 = col0 < g.dout, c1 = col1 < g.dout;
+    const bool any1 = 32 * (wave + 4) < g.dout;           // uniform over the wavefront
+    for (int seg = 0; seg < nseg; ++seg) {
+        const float* As = seg == 0 ? Zs : Xs;
+        const float* W = seg == 0 ? g.w : g.ws;
+        constexpr int KU = 8;                               // k-steps (of 2) per batch of loads
+        for (int32_t k0 = 0; k0 < din; k0 += 2 * KU) {
+            float b0[KU], b1[KU], a0[KU], a1[KU];
+#pragma unroll
+            for (int u = 0; u < KU; ++u) {
+                const int32_t k = k0 + 2 * u + half;
+                const bool kin = k < din;
+                const float* wr = W + (int64_t)(kin ? k : 0) * g.dout;
+                b0[u] = (kin && c0) ? wr[col0] : 0.f;
+                b1[u] = (kin && c1) ? wr[col1] : 0.f;
+                a0[u] = kin ? As[xl * g.kp + k] : 0.f;
+                a1[u] = kin ? As[(32 + xl) * g.kp + k] : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < KU; ++u) {
+                acc2[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[u], b0[u], acc2[0][0], 0, 0, 0);
+                acc2[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[u], b0[u], acc2[1][0], 0, 0, 0);
+                if (any1) {
+                    acc2[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[u], b1[u], acc2[0][1], 0, 0, 0);
+                    acc2[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[u], b1[u], acc2[1][1], 0, 0, 0);
+                }
+            }
+        }
+    }
+    // ---- epilogue: lane holds C[8 (r/4) + 4 (lane/32) + r%4][lane%32] of each 32x32 tile
+    __shared__ int32_t tile_row[TM];
+    if (threadIdx.x < TM) {
+        const int64_t li = tile0 + threadIdx.x;
+        int32_t row = -1;
+        if (li < sp.it.nshort) row = sp.it.rows_sorted[li];
+        else if (li < nrows) row = sp.it.long_row[li - sp.it.nshort];
+        tile_row[threadIdx.x] = row;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int32_t col = j == 0 ? col0 : col1;
+        if (col >= g.dout) continue;
+        const float bv = g.bias ? g.bias[col] : 0.f;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int tr = 32 * i + 8 * (r >> 2) + 4 * half + (r & 3);
+                const int32_t row = tile_row[tr];
+                if (row < 0) continue;
+                float v = acc2[i][j][r] + bv;
+                if (g.relu) v = v > 0.f ? v : 0.f;
+                g.y[(int64_t)row * g.dout + col] = v;
+            }
+    }
+}
+
 // out[row,:] = rowscale[row] * (partial[first,:] + partial[first+1,:] + ...): one wavefront per
 // long row and 256-column block, segments added in ascending order (eight loads in flight per
 // lane).
@@ -725,6 +928,60 @@ void launch_spmm_reduce(const float* rowscale, void* out, int32_t d, int out_bf1
     if (items.nlong <= 0 || d <= 0) return;
     if (out_bf16) spmm_reduce_typed<uint16_t>(rowscale, out, d, items, partial, sc, s);
     else spmm_reduce_typed<float>(rowscale, out, d, items, partial, sc, s);
+}
+
+bool spmm_gemm_fused_init();
+
+bool spmm_gemm_fused_ok(int32_t din, int32_t dout, const SpmmItems& items)
+{
+    const char* e = std::getenv("GNNMI_FUSE_AGG");       // read per call: tests flip it
+    const bool on = !(e && e[0] == '0');
+    return on && din % 4 == 0 && din > 32 && din <= 128 && dout >= 1 && dout <= 256 && items.rows_sorted &&
+           items.nshort + items.nlong > 0 && spmm_gemm_fused_init();
+}
+
+void launch_spmm_long_rows(const int64_t* rp, const int32_t* col, const float* w, const float* rowscale,
+                           const float* a_rows, int64_t n_a, const float* b_rows, int32_t din,
+                           const SpmmItems& items, float* partial, float* zlong, hipStream_t s)
+{
+    if (items.nsegs <= 0) return;
+    SpmmItems seg_only = items;
+    seg_only.nshort = 0;
+    seg_only.nranges = 0;
+    launch_spmm(rp, col, w, rowscale, a_rows, n_a, b_rows, zlong, n_a, din, 0, 0, seg_only, partial, 1,
+                SpmmScatter{}, s);
+    launch_spmm_reduce(rowscale, zlong, din, 0, items, partial, SpmmScatter{}, s);
+}
+
+void launch_spmm_gemm_fused(const int64_t* rp, const int32_t* col, const float* w, const float* rowscale,
+                            const float* a_rows, int64_t n_a, const float* b_rows, int32_t din,
+                            const SpmmItems& items, const float* zlong, const float* xself,
+                            const float* W, const float* Ws, const float* bias, int relu, float* y,
+                            int32_t dout, hipStream_t s)
+{
+    FusedArgs g{};
+    g.sp.rp = rp; g.sp.col = col; g.sp.w = w; g.sp.rowscale = rowscale;
+    g.sp.a_rows = a_rows; g.sp.n_a = n_a; g.sp.b_rows = b_rows; g.sp.out = nullptr;
+    g.sp.d = din; g.sp.ld = din; g.sp.it = items; g.sp.partial = nullptr;
+    g.sp.map_n_own = -1; g.sp.map_base = 0; g.sp.map_idx = nullptr; g.sp.bias = nullptr; g.sp.relu = 0;
+    g.zlong = zlong; g.xself = xself; g.w = W; g.ws = Ws; g.bias = bias; g.y = y; g.dout = dout; g.relu = relu;
+    g.kp = din + 1;
+    const int64_t nrows = items.nshort + items.nlong;
+    const dim3 grid((unsigned)((nrows + 63) / 64));
+    const size_t lds = (size_t)64 * (size_t)g.kp * sizeof(float) * (xself ? 2 : 1);
+    if (din <= 64) hipLaunchKernelGGL((k_agg_gemm<16>), grid, dim3(kBlock), lds, s, g);
+    else hipLaunchKernelGGL((k_agg_gemm<32>), grid, dim3(kBlock), lds, s, g);
+}
+
+// largest dynamic LDS the fused kernel may ask for: 64 rows x 129 floats, twice (GraphSAGE)
+bool spmm_gemm_fused_init()
+{
+    constexpr int kMaxLds = 2 * 64 * 129 * 4;
+    static const bool ok =
+        hipFuncSetAttribute((const void*)k_agg_gemm<16>, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds) == hipSuccess &&
+        hipFuncSetAttribute((const void*)k_agg_gemm<32>, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds) == hipSuccess;
+    if (!ok) (void)hipGetLastError();
+    return ok;
 }
 
 void launch_scatter_add(const float* src, int64_t nrows, int64_t n_own, int64_t base_row,

@@ -968,11 +968,16 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
             // whole arrays still in the pool, else through transfer buffers.
             Resident* gin = find_array(E, keep[2]);
             Resident* ain = l < L ? find_array(E, keep[3]) : nullptr;
-            Resident* srcarr = find_array(E, keep[1]);
+            Resident* srcarr = nullptr;
             Resident* gout = nullptr;
+            // A^{l-1} is read in both sweeps: a whole array if it fits beside what is there; then
+            // the output grad A^{l-1}, which the layer below reads next
+            if ((st = ensure_array(c, E, keep[1], a_slot, act_row_bytes(l - 1), act_host(l - 1), false, keep, 4,
+                                   nullptr, 0, true, &srcarr)) != GNN_OK) return st;
             if (need_prev && (st = ensure_array(c, E, keep[0], g_slot, (int64_t)din * 4, (char*)c->gact[(size_t)l - 2],
                                                 false, keep, 4, nullptr, 0, true, &gout)) != GNN_OK) return st;
             const bool sage = c->model == GNN_SAGE_MEAN;
+            const bool hidden_sage = sage && need_prev && l < L;    // its second sweep takes dY_p again
             const int64_t in_row = act_row_bytes(l - 1);
             auto block = [&](int32_t t, int i, BlockReq& r) -> gnn_status {
                 const int32_t p = M.sched[(size_t)t];
@@ -1000,26 +1005,27 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
                           });
             if (st != GNN_OK) return st;
             st = xf_sweep([&](int32_t t, int i, BlockReq& r) -> gnn_status {
-                              if (i == 1) return GNN_OK;
-                              if (i == 0 && !(sage && l == L && need_prev)) return GNN_OK;   // dY of a GraphSAGE output layer
+                              if (i == 1 && !hidden_sage) return GNN_OK;
+                              // dY of a GraphSAGE layer: grad A^L itself, or taken again from grad A^l and A^l
+                              if (i == 0 && !((sage && l == L && need_prev) || hidden_sage)) return GNN_OK;
                               return block(t, i, r);
                           },
                           [&](int32_t t, const BlockReq* b) -> gnn_status {
                               const int32_t p = M.sched[(size_t)t];
                               const int64_t r0 = M.off[(size_t)p], np = M.off[(size_t)p + 1] - r0;
                               if (!need_prev) {
-                                  xf_transform_bwd(c, l, p, b[2].dev, (const float*)b[0].dev, nullptr, s);
+                                  xf_transform_bwd(c, l, p, b[2].dev, (const float*)b[0].dev, nullptr, nullptr, s);
                                   return GNN_OK;
                               }
                               char* host_rows = (char*)(c->gact[(size_t)l - 2] + r0 * din);
                               gnn_status r_st;
                               if (gout) {
-                                  xf_transform_bwd(c, l, p, b[2].dev, (const float*)b[0].dev, (float*)gout->bc.ptr(p), s);
+                                  xf_transform_bwd(c, l, p, b[2].dev, (const float*)b[0].dev, b[1].dev, (float*)gout->bc.ptr(p), s);
                                   return produced(gout, p, host_rows, np * din * 4);
                               }
                               const int ob = t & 1;
                               if ((r_st = wait_out_free(ob)) != GNN_OK) return r_st;
-                              xf_transform_bwd(c, l, p, b[2].dev, (const float*)b[0].dev, (float*)E.outbuf(ob), s);
+                              xf_transform_bwd(c, l, p, b[2].dev, (const float*)b[0].dev, b[1].dev, (float*)E.outbuf(ob), s);
                               return store_out(ob, host_rows, np * din * 4);
                           });
             if (st != GNN_OK) return st;

@@ -194,6 +194,12 @@ EDGE = [
     ("sage", (12, 12, 4), 64, 300, True, 64, "user", True),        # k = n: every vertex alone
     ("gcn", (132, 260, 70), 700, 9000, True, 5, "lp", True),       # several GEMM tiles + ragged tails
     ("sage", (1028, 16, 4), 200, 1500, True, 2, "random", True),   # rows wider than 1024 floats
+    # aggregation fused with the transform (d_in in 36..128, d_out <= 256): 16 and 32 lanes per row,
+    # ragged last 32-column tile, one and two column tiles per wavefront, an output narrower than a tile
+    ("gcn", (36, 33, 5), 700, 6000, True, 3, "lp", True),
+    ("sage", (68, 256, 3), 900, 9000, False, 4, "random", True),
+    ("gcn", (128, 250, 7), 1100, 12000, True, 2, "lp", False),
+    ("sage", (100, 129, 64, 9), 800, 7000, True, 5, "random", True),
 ]
 
 
@@ -214,6 +220,43 @@ def test_edge_shapes(case):
         ref = ref_nb
     assert abs(loss - ref["loss"]) <= TOL * abs(ref["loss"])
     compare(s.results(), ref, model, has_bias=has_bias, tag=str(case))
+
+
+@pytest.mark.parametrize("model,dims", [("gcn", (128, 128, 40)), ("sage", (100, 256, 47))])
+def test_fused_aggregation_and_transform(monkeypatch, model, dims):
+    """Aggregate-first layers with d_in <= 128 run the aggregation and the contraction in one
+    kernel, the aggregated rows staying in LDS.  On a graph whose hubs are cut into segments
+    (rows of more than 512 entries reach the kernel through the long-row pass): against the
+    oracle, and against the same epoch with the fusion switched off (same sums up to their
+    order)."""
+    say("case fused aggregate+transform %s %s" % (model, dims))
+    from paper_2605_11517_amd import Session
+    n = 2500
+    rowptr, colidx = small_graph(n, 90000, seed=51, symmetric=True, self_loops=False)
+    assert np.diff(rowptr).max() > 512 and np.diff(rowptr).min() == 0
+    cfg = dict(model=model, dims=dims, seed=9, train_frac=0.5)
+    X, y, m, w = make_inputs(cfg, n)
+    ref = og.epoch(model, rowptr, colidx, dims, X, w, y, m)
+    res = {}
+    for fuse in ("1", "0"):
+        monkeypatch.setenv("GNNMI_FUSE_AGG", fuse)
+        s = Session(model, dims, rowptr, colidx, 3, "lp", 4, X, w, y, m)
+        s.ctx.set_profiling(1)
+        loss = s.epoch()
+        assert s.epoch() == loss
+        prof = s.ctx.get_profile()
+        # the first layer's forward contraction is part of the aggregation kernel when fused
+        k, L = 3, len(dims) - 1
+        fused = sum(1 for l in range(L) if dims[l] % 4 == 0 and 32 < dims[l] <= 128 and dims[l + 1] <= 256)
+        assert fused >= 1
+        want = (L - fused) * k if fuse == "1" else L * k
+        assert prof["gemm_fwd"][1] == want, (fuse, prof["gemm_fwd"])
+        res[fuse] = s.results()
+        assert abs(loss - ref["loss"]) <= TOL * abs(ref["loss"])
+        compare(res[fuse], ref, model, tag="fused=" + fuse)
+    for key in ("act", "gW", "gact"):
+        for a, b in zip(res["1"][key], res["0"][key]):
+            assert rel_err(a, b) <= 1e-5, key
 
 
 BF16_TOL = 2e-2
@@ -335,7 +378,7 @@ def test_streaming_schedule_is_bit_identical_to_resident(case):
 
 
 @pytest.mark.parametrize("name,dims,extra", [
-    ("mini_sage", (100, 256, 256, 47), 1.0),            # hidden GraphSAGE layer keeps its dY rows; padded 48-wide output
+    ("mini_sage", (100, 256, 256, 47), 1.0),            # hidden GraphSAGE layer takes its dY rows twice; padded 48-wide output
     ("mini_sage", (100, 256, 256, 47), 3.0),
     ("mini_gcn_directed", (128, 128, 128, 172), 1.0),
     ("tiny", (64, 64, 16), 2.0),
@@ -363,8 +406,7 @@ def test_streaming_transform_first_layers_are_bit_identical_to_resident(name, di
     rnd = lambda b: (b + 255) // 256 * 256
     pad = lambda d: (d + 3) // 4 * 4
     hp = max(pad(dims[l]) for l in range(1, L + 1) if order[l - 1])
-    dyw = max([pad(dims[l]) for l in range(2, L) if order[l - 1] and cfg["model"] == "sage"] or [0])
-    xf_bytes = rnd(n * hp * 4) + rnd(n * dyw * 4)
+    xf_bytes = rnd(n * hp * 4)
     minimum = 4 * rnd(max(1, st["max_own"]) * max(dims) * 4)
     s = Session(cfg["model"], dims, rowptr, colidx, cfg["k"], cfg["part"], cfg["seed"], X, w, y, m,
                 layer_order="auto", hbm_budget_bytes=int(xf_bytes + minimum * extra))
