@@ -87,7 +87,7 @@ def algorithmic_bytes(stats, dims, model, n_parts, es=4, fused_scatter=False, xf
 def fused_layers(dims, xf, dtype):
     """Layers (0-based) whose forward contraction runs inside the aggregation kernel (the
     aggregated tile stays in LDS); mirrors spmm_gemm_fused_ok() of the library."""
-    if dtype != "f32" or os.environ.get("GNNMI_FUSE_AGG", "1")[:1] == "0":
+    if dtype != "f32" or os.environ.get("GNNMI_FUSE_AGG", "0")[:1] != "1":
         return []
     return [l for l in range(len(dims) - 1)
             if not xf[l] and dims[l] % 4 == 0 and 32 < dims[l] <= 128 and dims[l + 1] <= 256]

@@ -126,18 +126,17 @@ void launch_spmm(const int64_t* rp, const int32_t* col, const float* w, const fl
 // Aggregation fused with the transform, fp32: y[r,:] = act(Z[r,:] W (+ xself[r,:] Ws) + bias) with
 // Z as launch_spmm would compute it, kept in LDS.  zlong: n_a x din floats of scratch for the
 // rows that are cut into segments.  Only when spmm_gemm_fused_ok() (d_in in 36..128, a multiple
-// of 4; d_out <= 256; GNNMI_FUSE_AGG=0 switches it off).
+// of 4; d_out <= 256; and GNNMI_FUSE_AGG=1: measured slower than the two kernels it replaces).
 bool spmm_gemm_fused_ok(int32_t din, int32_t dout, const SpmmItems& items);
-// first the rows that are cut into segments (partial sums, combined into their rows of zlong) ...
-void launch_spmm_long_rows(const int64_t* rp, const int32_t* col, const float* w, const float* rowscale,
-                           const float* a_rows, int64_t n_a, const float* b_rows, int32_t din,
-                           const SpmmItems& items, float* partial, float* zlong, hipStream_t s);
-// ... then every row: aggregate (or fetch from zlong), transform, store
+// stage 0: one launch whose first workgroups take the 512-entry segments of the long rows
+// (partial sums into `partial`) and whose other workgroups aggregate and transform the short rows;
+// stage 1: the long rows' partial sums are combined into their rows of zlong; stage 2: those rows
+// are transformed (a launch of a few workgroups).
 void launch_spmm_gemm_fused(const int64_t* rp, const int32_t* col, const float* w, const float* rowscale,
                             const float* a_rows, int64_t n_a, const float* b_rows, int32_t din,
-                            const SpmmItems& items, const float* zlong, const float* xself,
+                            const SpmmItems& items, float* partial, float* zlong, const float* xself,
                             const float* W, const float* Ws, const float* bias, int relu, float* y,
-                            int32_t dout, hipStream_t s);
+                            int32_t dout, int stage, hipStream_t s);
 // second step of the aggregation: combines the segment partial sums of the long rows
 void launch_spmm_reduce(const float* rowscale, void* out, int32_t d, int out_bf16,
                         const SpmmItems& items, float* partial, const SpmmScatter& sc, hipStream_t s);

@@ -505,6 +505,8 @@ struct FusedArgs {
     float* y;               // [n_p, d_out]
     int32_t dout, relu;
     int32_t kp;             // LDS row stride in floats (odd)
+    int32_t seg_blocks;     // the first seg_blocks workgroups compute segment partial sums instead
+    int32_t long_only;      // 1: the tiles cover the long rows only (second launch), 0: the short rows only
 };
 
 template <int G>
@@ -521,13 +523,73 @@ __global__ __launch_bounds__(kBlock) void k_agg_gemm(const FusedArgs g)
     const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
     const int slot = lane / G, gl = lane % G;
     const int32_t din = sp.d;
-    const int64_t nrows = sp.it.nshort + sp.it.nlong;
-    const int64_t tile0 = (int64_t)blockIdx.x * TM;
+    // list of rows this launch tiles: the short rows (degree-sorted), or the long rows
+    const int64_t nrows = g.long_only ? sp.it.nlong : sp.it.nshort;
     const float* a_rows = static_cast<const float*>(sp.a_rows);
     const float* b_rows = static_cast<const float*>(sp.b_rows);
     const int coff = gl * 4;
     const bool live = coff < din;
     const int cload = live ? coff : 0;
+
+    if ((int32_t)blockIdx.x < g.seg_blocks) {
+        // segment role: one 512-entry segment of a long row per slot -> fp32 partial sum; the
+        // long-row kernel combines them afterwards and a second launch transforms those rows
+        const int64_t item = ((int64_t)blockIdx.x * (kBlock / kWave) + wave) * S + slot;
+        int64_t e_begin = 0;
+        int32_t len = 0;
+        if (item < sp.it.nsegs) {
+            e_begin = sp.it.seg_begin[item];
+            len = sp.it.seg_len[item];
+        }
+        int32_t maxlen = len;
+        int lead = slot;
+#pragma unroll
+        for (int m = G; m < kWave; m <<= 1) {
+            const int32_t ol = __shfl_xor(maxlen, m, kWave);
+            const int os = __shfl_xor(lead, m, kWave);
+            if (ol > maxlen || (ol == maxlen && os < lead)) { maxlen = ol; lead = os; }
+        }
+        float acc[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int32_t e0 = 0; e0 < maxlen; e0 += G) {
+            int32_t my_c = 0;
+            float my_w = 0.f;
+            if (e0 + gl < len) {
+                my_c = sp.col[e_begin + e0 + gl];
+                my_w = sp.w ? sp.w[e_begin + e0 + gl] : 1.f;
+            }
+            const int cnt = len - e0;
+            const int lead_cnt = maxlen - e0 < G ? maxlen - e0 : G;
+#pragma unroll
+            for (int j0 = 0; j0 < G; j0 += UNROLL) {
+                if (j0 >= lead_cnt) break;
+                float4 x[UNROLL];
+                float ww[UNROLL];
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) {
+                    const int j = j0 + u;
+                    const bool on = j < cnt;
+                    const int src_lane = on ? slot * G + j : lead * G + (j < lead_cnt ? j : lead_cnt - 1);
+                    const int32_t c = __shfl(my_c, src_lane, kWave);
+                    const float wt = __shfl(my_w, src_lane, kWave);
+                    ww[u] = on ? wt : 0.f;
+                    const float* src = (c < sp.n_a) ? a_rows + (int64_t)c * sp.ld : b_rows + ((int64_t)c - sp.n_a) * sp.ld;
+                    x[u] = *reinterpret_cast<const float4*>(src + cload);
+                }
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) {
+                    const bool on = (j0 + u) < cnt;
+                    acc[0] += on ? ww[u] * x[u].x : 0.f;
+                    acc[1] += on ? ww[u] * x[u].y : 0.f;
+                    acc[2] += on ? ww[u] * x[u].z : 0.f;
+                    acc[3] += on ? ww[u] * x[u].w : 0.f;
+                }
+            }
+        }
+        if (live && item < sp.it.nsegs)
+            *reinterpret_cast<float4*>(sp.partial + item * (int64_t)sp.ld + coff) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+        return;
+    }
+    const int64_t tile0 = ((int64_t)blockIdx.x - g.seg_blocks) * TM;
 
     // ---- phase 1: sums of this wavefront's 16 rows, S at a time
     for (int r0 = 0; r0 < RPW; r0 += S) {
@@ -537,13 +599,15 @@ __global__ __launch_bounds__(kBlock) void k_agg_gemm(const FusedArgs g)
         int64_t e_begin = 0;
         int32_t len = 0;
         bool is_long = false;
-        if (li < sp.it.nshort) {
-            row = sp.it.rows_sorted[li];
-            e_begin = sp.rp[row];
-            len = (int32_t)(sp.rp[row + 1] - e_begin);
-        } else if (li < nrows) {
-            row = sp.it.long_row[li - sp.it.nshort];
-            is_long = true;
+        if (li < nrows) {
+            if (g.long_only) {
+                row = sp.it.long_row[li];
+                is_long = true;
+            } else {
+                row = sp.it.rows_sorted[li];
+                e_begin = sp.rp[row];
+                len = (int32_t)(sp.rp[row + 1] - e_begin);
+            }
         }
         int32_t maxlen = len;
         int lead = slot;
@@ -629,7 +693,7 @@ __global__ __launch_bounds__(kBlock) void k_agg_gemm(const FusedArgs g)
     for (int seg = 0; seg < nseg; ++seg) {
         const float* As = seg == 0 ? Zs : Xs;
         const float* W = seg == 0 ? g.w : g.ws;
-        constexpr int KU = 8;                               // k-steps (of 2) per batch of loads
+        constexpr int KU = 16;                              // k-steps (of 2) per batch of loads
         for (int32_t k0 = 0; k0 < din; k0 += 2 * KU) {
             float b0[KU], b1[KU], a0[KU], a1[KU];
 #pragma unroll
@@ -658,8 +722,7 @@ __global__ __launch_bounds__(kBlock) void k_agg_gemm(const FusedArgs g)
     if (threadIdx.x < TM) {
         const int64_t li = tile0 + threadIdx.x;
         int32_t row = -1;
-        if (li < sp.it.nshort) row = sp.it.rows_sorted[li];
-        else if (li < nrows) row = sp.it.long_row[li - sp.it.nshort];
+        if (li < nrows) row = g.long_only ? sp.it.long_row[li] : sp.it.rows_sorted[li];
         tile_row[threadIdx.x] = row;
     }
     __syncthreads();
@@ -934,43 +997,50 @@ bool spmm_gemm_fused_init();
 
 bool spmm_gemm_fused_ok(int32_t din, int32_t dout, const SpmmItems& items)
 {
-    const char* e = std::getenv("GNNMI_FUSE_AGG");       // read per call: tests flip it
-    const bool on = !(e && e[0] == '0');
+    // Off unless GNNMI_FUSE_AGG=1 (read per call: tests flip it).  Measured on the 50 M-vertex
+    // GCN workload the fused forward pass of layer 1 takes 0.63 ms more per partition than the
+    // stand-alone aggregation and saves a 0.29 ms contraction (epoch 1051 against 1025 ms; on the
+    // 2.4 M-vertex GraphSAGE workload 105 against 99.8 ms): its row fetches lose the column
+    // slicing across XCDs, and the LDS tile limits a CU to three or four workgroups.
+    const char* e = std::getenv("GNNMI_FUSE_AGG");
+    const bool on = e && e[0] == '1';
     return on && din % 4 == 0 && din > 32 && din <= 128 && dout >= 1 && dout <= 256 && items.rows_sorted &&
            items.nshort + items.nlong > 0 && spmm_gemm_fused_init();
 }
 
-void launch_spmm_long_rows(const int64_t* rp, const int32_t* col, const float* w, const float* rowscale,
-                           const float* a_rows, int64_t n_a, const float* b_rows, int32_t din,
-                           const SpmmItems& items, float* partial, float* zlong, hipStream_t s)
-{
-    if (items.nsegs <= 0) return;
-    SpmmItems seg_only = items;
-    seg_only.nshort = 0;
-    seg_only.nranges = 0;
-    launch_spmm(rp, col, w, rowscale, a_rows, n_a, b_rows, zlong, n_a, din, 0, 0, seg_only, partial, 1,
-                SpmmScatter{}, s);
-    launch_spmm_reduce(rowscale, zlong, din, 0, items, partial, SpmmScatter{}, s);
-}
-
 void launch_spmm_gemm_fused(const int64_t* rp, const int32_t* col, const float* w, const float* rowscale,
                             const float* a_rows, int64_t n_a, const float* b_rows, int32_t din,
-                            const SpmmItems& items, const float* zlong, const float* xself,
+                            const SpmmItems& items, float* partial, float* zlong, const float* xself,
                             const float* W, const float* Ws, const float* bias, int relu, float* y,
-                            int32_t dout, hipStream_t s)
+                            int32_t dout, int stage, hipStream_t s)
 {
     FusedArgs g{};
     g.sp.rp = rp; g.sp.col = col; g.sp.w = w; g.sp.rowscale = rowscale;
     g.sp.a_rows = a_rows; g.sp.n_a = n_a; g.sp.b_rows = b_rows; g.sp.out = nullptr;
-    g.sp.d = din; g.sp.ld = din; g.sp.it = items; g.sp.partial = nullptr;
+    g.sp.d = din; g.sp.ld = din; g.sp.it = items; g.sp.partial = partial;
     g.sp.map_n_own = -1; g.sp.map_base = 0; g.sp.map_idx = nullptr; g.sp.bias = nullptr; g.sp.relu = 0;
     g.zlong = zlong; g.xself = xself; g.w = W; g.ws = Ws; g.bias = bias; g.y = y; g.dout = dout; g.relu = relu;
     g.kp = din + 1;
-    const int64_t nrows = items.nshort + items.nlong;
-    const dim3 grid((unsigned)((nrows + 63) / 64));
     const size_t lds = (size_t)64 * (size_t)g.kp * sizeof(float) * (xself ? 2 : 1);
-    if (din <= 64) hipLaunchKernelGGL((k_agg_gemm<16>), grid, dim3(kBlock), lds, s, g);
-    else hipLaunchKernelGGL((k_agg_gemm<32>), grid, dim3(kBlock), lds, s, g);
+    const int G = din <= 64 ? 16 : 32;
+    const int64_t per_block = (int64_t)(kBlock / kWave) * (kWave / G);      // segments per workgroup
+    if (stage == 0) {
+        // segments first in the grid (they are the longest items), then the short rows in tiles of 64
+        g.seg_blocks = (int32_t)((items.nsegs + per_block - 1) / per_block);
+        g.long_only = 0;
+        const int64_t blocks = g.seg_blocks + (items.nshort + 63) / 64;
+        if (blocks <= 0) return;
+        if (G == 16) hipLaunchKernelGGL((k_agg_gemm<16>), dim3((unsigned)blocks), dim3(kBlock), lds, s, g);
+        else hipLaunchKernelGGL((k_agg_gemm<32>), dim3((unsigned)blocks), dim3(kBlock), lds, s, g);
+    } else if (stage == 1) {
+        launch_spmm_reduce(rowscale, zlong, din, 0, items, partial, SpmmScatter{}, s);
+    } else if (items.nlong > 0) {
+        g.seg_blocks = 0;
+        g.long_only = 1;
+        const dim3 grid((unsigned)((items.nlong + 63) / 64));
+        if (G == 16) hipLaunchKernelGGL((k_agg_gemm<16>), grid, dim3(kBlock), lds, s, g);
+        else hipLaunchKernelGGL((k_agg_gemm<32>), grid, dim3(kBlock), lds, s, g);
+    }
 }
 
 // largest dynamic LDS the fused kernel may ask for: 64 rows x 129 floats, twice (GraphSAGE)

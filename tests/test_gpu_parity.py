@@ -204,9 +204,10 @@ EDGE = [
 
 
 @pytest.mark.parametrize("case", EDGE, ids=lambda c: "%s-%s-k%d" % (c[0], "x".join(map(str, c[1])), c[5]))
-def test_edge_shapes(case):
+def test_edge_shapes(monkeypatch, case):
     model, dims, n, m_draw, sym, k, mode, has_bias = case
     say("case edge %s" % (case,))
+    monkeypatch.setenv("GNNMI_FUSE_AGG", "1")       # where the widths allow it (off by default)
     rowptr, colidx = small_graph(n, m_draw, seed=31, symmetric=sym, self_loops=False)
     cfg = dict(model=model, dims=dims, seed=77, train_frac=0.5)
     X, y, m, w = make_inputs(cfg, n)
@@ -224,8 +225,9 @@ def test_edge_shapes(case):
 
 @pytest.mark.parametrize("model,dims", [("gcn", (128, 128, 40)), ("sage", (100, 256, 47))])
 def test_fused_aggregation_and_transform(monkeypatch, model, dims):
-    """Aggregate-first layers with d_in <= 128 run the aggregation and the contraction in one
-    kernel, the aggregated rows staying in LDS.  On a graph whose hubs are cut into segments
+    """With GNNMI_FUSE_AGG=1 aggregate-first layers with d_in <= 128 run the aggregation and the
+    contraction in one kernel, the aggregated rows staying in LDS (off by default: measured
+    slower than the two kernels).  On a graph whose hubs are cut into segments
     (rows of more than 512 entries reach the kernel through the long-row pass): against the
     oracle, and against the same epoch with the fusion switched off (same sums up to their
     order)."""
@@ -385,10 +387,11 @@ def test_streaming_schedule_is_bit_identical_to_resident(case):
     ("mini_sage", (64, 32, 32, 8), 1.0),                # every layer transforms first
 ])
 def test_streaming_transform_first_layers_are_bit_identical_to_resident(name, dims, extra):
-    """Layer order by rows moved in the streaming schedule: the whole-graph buffers of the
-    transform-first layers come out of the HBM budget, the rest is the block cache (`extra` times
-    its minimum).  Same bits as the resident schedule with the same order; with a budget that
-    cannot hold those buffers the schedule falls back to the paper's order for every layer."""
+    """Layer order by rows moved in the streaming schedule: the whole-graph buffer of the
+    transform-first layers comes out of the HBM budget, the rest is the pool (`extra` times the
+    least the rule asks for: two whole arrays of the widest layer and the smallest block cache).
+    Same bits as the resident schedule with the same order; with a budget below that the
+    schedule keeps the paper's order for every layer."""
     say("case streaming transform-first %s %s x%g" % (name, dims, extra))
     from paper_2605_11517_amd import Session
     cfg, rowptr, colidx = make_config(name)
@@ -407,7 +410,9 @@ def test_streaming_transform_first_layers_are_bit_identical_to_resident(name, di
     pad = lambda d: (d + 3) // 4 * 4
     hp = max(pad(dims[l]) for l in range(1, L + 1) if order[l - 1])
     xf_bytes = rnd(n * hp * 4)
-    minimum = 4 * rnd(max(1, st["max_own"]) * max(dims) * 4)
+    blk = rnd(max(1, st["max_own"]) * max(dims) * 4)
+    # room for two whole arrays of the widest layer beside the buffer, plus the smallest block cache
+    minimum = 2 * cfg["k"] * blk + 4 * blk
     s = Session(cfg["model"], dims, rowptr, colidx, cfg["k"], cfg["part"], cfg["seed"], X, w, y, m,
                 layer_order="auto", hbm_budget_bytes=int(xf_bytes + minimum * extra))
     assert [s.ctx.layer_is_transform_first(l) for l in range(1, L + 1)] == order
@@ -422,7 +427,7 @@ def test_streaming_transform_first_layers_are_bit_identical_to_resident(name, di
                 assert np.array_equal(a, b), (rep, key, l)
     ref = og.epoch(cfg["model"], rowptr, colidx, dims, X, w, y, m)
     compare(got, ref, cfg["model"], tag="streaming transform-first " + name)
-    # one byte short of the buffers plus the smallest cache: every layer keeps the paper's order
+    # 256 bytes short of that: every layer keeps the paper's order
     s2 = Session(cfg["model"], dims, rowptr, colidx, cfg["k"], cfg["part"], cfg["seed"], X, w, y, m,
                  layer_order="auto", hbm_budget_bytes=int(xf_bytes + minimum - 256))
     assert not any(s2.ctx.layer_is_transform_first(l) for l in range(1, L + 1))
