@@ -39,7 +39,12 @@ def short_name(name: str) -> str:
 
 
 def _one(pattern):
+    """The first file matching `pattern`, also in sub-directories of its directory (rocprofv3
+    may put its files under a directory named after the host)."""
     hits = sorted(glob.glob(pattern))
+    if not hits:
+        d, base = os.path.split(pattern)
+        hits = sorted(glob.glob(os.path.join(d, "**", base), recursive=True))
     if not hits:
         raise FileNotFoundError(pattern)
     return hits[0]
