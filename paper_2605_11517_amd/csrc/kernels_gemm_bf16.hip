@@ -585,6 +585,7 @@ struct ArgsT {
     int32_t m, n;
     int64_t k;                 // rows covered, a multiple of 64
     int64_t chunk;             // rows per split, a multiple of 64
+    int32_t splits;            // > 0: one-dimensional grid, see k_gemm_bf16_tn_wide
 };
 
 __device__ inline int tn_off(int k, int mcol)          // byte offset of element (k, mcol), mcol % 4 == 0
@@ -630,8 +631,21 @@ __global__ __launch_bounds__(WTHREADS) void k_gemm_bf16_tn_wide(const ArgsT g)
     extern __shared__ __attribute__((aligned(1024))) char wlds[];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave >> 2, wn = wave & 3;
-    const int32_t m0 = blockIdx.x * WBM, n0 = blockIdx.y * WBN;
-    const int64_t kbeg = (int64_t)blockIdx.z * g.chunk;
+    // One-dimensional grid (splits > 0): workgroups are dealt to the 8 XCDs round-robin, and
+    // every tile of one K split runs on the same XCD, so the 64-row stages of A and B that the
+    // tiles of a split share are fetched into that XCD's L2 once instead of once per tile.
+    int32_t bx = blockIdx.x, by = blockIdx.y, bz = blockIdx.z;
+    if (g.splits > 0) {
+        const int32_t mt = (g.m + WBM - 1) / WBM, nt = (g.n + WBN - 1) / WBN, tiles = mt * nt;
+        const int32_t slot = blockIdx.x >> 3, xcd = blockIdx.x & 7;
+        bz = (slot / tiles) * 8 + xcd;
+        if (bz >= g.splits) return;
+        const int32_t tile = slot % tiles;
+        bx = tile % mt;
+        by = tile / mt;
+    }
+    const int32_t m0 = bx * WBM, n0 = by * WBN;
+    const int64_t kbeg = (int64_t)bz * g.chunk;
     const int64_t kend = kbeg + g.chunk < g.k ? kbeg + g.chunk : g.k;
     const int nstages = kend > kbeg ? (int)((kend - kbeg) / WBK) : 0;
 
@@ -673,7 +687,7 @@ __global__ __launch_bounds__(WTHREADS) void k_gemm_bf16_tn_wide(const ArgsT g)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bv[j], acc[i][j], 0, 0, 0);
         }
     }
-    float* out = g.partial + (int64_t)blockIdx.z * g.m * g.n;
+    float* out = g.partial + (int64_t)bz * g.m * g.n;
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -779,8 +793,19 @@ void launch_gemm_bf16_tn(const void* a, int64_t lda, const void* b, int64_t ldb,
             const int want = wide_tn_splits(kdim, m, n);
             w.chunk = (w.k / WBK + want - 1) / want * WBK;
             const int sp = (int)((w.k + w.chunk - 1) / w.chunk);
-            hipLaunchKernelGGL(k_gemm_bf16_tn_wide, dim3((unsigned)((m + WBM - 1) / WBM), (unsigned)((n + WBN - 1) / WBN),
-                                                         (unsigned)sp), dim3(WTHREADS), TLDS, s, w);
+            static const bool by_split = [] {
+                const char* e = getenv("GNNMI_GEMM_TN_XCD");
+                return !(e && e[0] == '0');
+            }();
+            const unsigned mt = (unsigned)((m + WBM - 1) / WBM), nt = (unsigned)((n + WBN - 1) / WBN);
+            if (by_split && mt * nt > 1) {
+                w.splits = sp;
+                hipLaunchKernelGGL(k_gemm_bf16_tn_wide, dim3((unsigned)((sp + 7) / 8 * 8) * mt * nt), dim3(WTHREADS),
+                                   TLDS, s, w);
+            } else {
+                w.splits = 0;
+                hipLaunchKernelGGL(k_gemm_bf16_tn_wide, dim3(mt, nt, (unsigned)sp), dim3(WTHREADS), TLDS, s, w);
+            }
             launch_reduce_partials(partial, sp, (int64_t)m * n, c, ldc, m, n, s);
             if (w.k == kdim) return;
             a = (const bf16_t*)a + w.k * lda;
