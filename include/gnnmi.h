@@ -385,6 +385,8 @@ typedef struct {
     int64_t h2d_bytes, d2h_bytes;
     int64_t direct_gathers; /* (partition, source block) pairs whose boundary rows a kernel read */
     int64_t direct_bytes;   /* straight from the pinned host array, and their bytes (in h2d_bytes) */
+    int64_t direct_scatters;      /* (partition, owner block) pairs whose gradient rows a kernel added */
+    int64_t direct_scatter_bytes; /* straight in the pinned host array; bytes read + written (in h2d/d2h_bytes) */
 } gnn_stream_stats;
 gnn_status gnn_get_stream_stats(const gnn_ctx *ctx, gnn_stream_stats *out);
 

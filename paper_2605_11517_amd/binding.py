@@ -57,7 +57,8 @@ def make_optimizer(kind="adam", lr=0.01, beta1=0.9, beta2=0.999, eps=1e-8, weigh
 class StreamStats(C.Structure):
     _fields_ = [(f, C.c_int64) for f in ("act_loads", "act_hits", "grad_loads", "grad_hits",
                                          "grad_writebacks", "h2d_bytes", "d2h_bytes",
-                                         "direct_gathers", "direct_bytes")]
+                                         "direct_gathers", "direct_bytes", "direct_scatters",
+                                         "direct_scatter_bytes")]
 
 
 def load_library():

@@ -60,6 +60,11 @@ struct BlockCache {
     const char* host_dev = nullptr; // the same memory as kernels see it (null: not mapped for the device)
     bool writeback = false;
     bool identity = false;          // a whole array: block p lives in slot p and is never evicted
+    // write-back cache whose host array kernels can reach: rows of blocks that are not cached are
+    // added to straight in host memory.  Per block: an event after the last such kernel (a later
+    // load of the block waits for it) and one after the last write-back (a later kernel waits)
+    std::vector<hipEvent_t> blk_direct, blk_flushed;
+    std::vector<uint8_t> has_blk_direct, has_blk_flushed;
     int32_t cur_t = 0;              // step (position in the partition order) whose accesses are being issued
     int64_t tick = 0;
     char* ptr(int32_t s) const { return pool + (int64_t)s * slot_bytes; }
@@ -92,6 +97,7 @@ struct StreamEngine {
     int32_t k = 0;
     int64_t h2d_bytes = 0, d2h_bytes = 0;   // of the running epoch
     int64_t direct_gathers = 0, direct_bytes = 0;   // boundary rows read straight from host memory
+    int64_t direct_scatters = 0, direct_scatter_bytes = 0;   // gradient rows added straight in host memory
     int64_t loads[2] = {0, 0}, hits[2] = {0, 0}, writebacks = 0;
     char* io = nullptr;             // 8 transfer buffers
     int64_t io_bytes = 0;           // bytes of one buffer
@@ -201,13 +207,24 @@ gnn_status configure(gnn_ctx* c, StreamEngine& E, BlockCache& bc, char* pool, in
     bc.row_bytes = row_bytes;
     bc.host = host;
     bc.host_dev = nullptr;
-    if (host && !writeback && !identity && direct_gather_enabled()) {
-        // pinned host memory that is mapped for the device can be read by kernels directly
+    if (host && !identity && direct_gather_enabled()) {
+        // pinned host memory that is mapped for the device can be read (and written) by kernels directly
         hipPointerAttribute_t at;
         if (hipPointerGetAttributes(&at, host) == hipSuccess && at.type == hipMemoryTypeHost && at.devicePointer)
             bc.host_dev = (const char*)at.devicePointer;
         else
             (void)hipGetLastError();
+    }
+    if (writeback && bc.host_dev) {
+        while ((int32_t)bc.blk_direct.size() < E.k) {
+            hipEvent_t a, b;
+            GNN_HIP(hipEventCreateWithFlags(&a, hipEventDisableTiming));
+            bc.blk_direct.push_back(a);
+            GNN_HIP(hipEventCreateWithFlags(&b, hipEventDisableTiming));
+            bc.blk_flushed.push_back(b);
+        }
+        bc.has_blk_direct.assign((size_t)E.k, 0);
+        bc.has_blk_flushed.assign((size_t)E.k, 0);
     }
     bc.writeback = writeback;
     bc.identity = identity;
@@ -246,6 +263,10 @@ gnn_status write_back(gnn_ctx* c, StreamEngine& E, BlockCache& bc, int32_t s)
                                hipMemcpyDeviceToHost, E.d2h));
     GNN_HIP(hipEventRecord(sl.flushed, E.d2h));
     sl.has_flushed = true;
+    if (!bc.blk_flushed.empty()) {
+        GNN_HIP(hipEventRecord(bc.blk_flushed[(size_t)sl.part], E.d2h));
+        bc.has_blk_flushed[(size_t)sl.part] = 1;
+    }
     sl.dirty = false;
     ++E.writebacks;
     E.d2h_bytes += np * bc.row_bytes;
@@ -331,6 +352,10 @@ gnn_status acquire(gnn_ctx* c, StreamEngine& E, BlockCache& bc, int32_t part, hi
         } else {
             if (sl.has_released) GNN_HIP(hipStreamWaitEvent(E.h2d, sl.released, 0));
             if (sl.has_flushed) GNN_HIP(hipStreamWaitEvent(E.h2d, sl.flushed, 0));
+            if (!bc.has_blk_direct.empty() && bc.has_blk_direct[(size_t)part])
+                GNN_HIP(hipStreamWaitEvent(E.h2d, bc.blk_direct[(size_t)part], 0));    // rows added in host memory
+            if (!bc.has_blk_flushed.empty() && bc.has_blk_flushed[(size_t)part])
+                GNN_HIP(hipStreamWaitEvent(E.h2d, bc.blk_flushed[(size_t)part], 0));   // its own last write-back
             if (np > 0)
                 GNN_HIP(hipMemcpyAsync(bc.ptr(s), bc.host + r0 * bc.row_bytes, (size_t)(np * bc.row_bytes),
                                        hipMemcpyHostToDevice, E.h2d));
@@ -640,6 +665,12 @@ void stream_engine_destroy(gnn_ctx* c)
     };
     drop(E->actc.slots);
     drop(E->gradc.slots);
+    for (BlockCache* bc : {&E->actc, &E->gradc}) {
+        for (hipEvent_t e : bc->blk_direct) (void)hipEventDestroy(e);
+        for (hipEvent_t e : bc->blk_flushed) (void)hipEventDestroy(e);
+        bc->blk_direct.clear();
+        bc->blk_flushed.clear();
+    }
     drop(E->spare);
     for (auto& r : E->arrays) drop(r->bc.slots);
     for (int i = 0; i < 2; ++i) {
@@ -681,6 +712,7 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
     E.h2d_bytes = E.d2h_bytes = 0;
     E.loads[0] = E.loads[1] = E.hits[0] = E.hits[1] = E.writebacks = 0;
     E.direct_gathers = E.direct_bytes = 0;
+    E.direct_scatters = E.direct_scatter_bytes = 0;
 
     zero_weight_grads(c, s);
 
@@ -1171,6 +1203,32 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
                     for (int32_t q = 0; q < k; ++q) {
                         const int64_t len = run[q + 1] - run[q];
                         if (len <= 0) continue;
+                        if (dst->host_dev && !dst->blk_direct.empty() && dst->slot_of[(size_t)q] < 0 &&
+                            !has_empty_slot(*dst)) {
+                            // The owner block is not cached and caching it would push out a block that
+                            // later partitions add to as well (each partition touches nearly every
+                            // owner): add these rows where the block lives, in the pinned host array
+                            // (the paper accumulates on the host too).  The kernel reads and writes
+                            // the rows over the link; stream order keeps the sum in partition order.
+                            const int64_t q0 = M.off[(size_t)q], nq = M.off[(size_t)q + 1] - q0;
+                            float* hostq = (float*)const_cast<char*>(dst->host_dev) + q0 * din;
+                            if (dst->has_blk_flushed[(size_t)q])
+                                GNN_HIP(hipStreamWaitEvent(s, dst->blk_flushed[(size_t)q], 0));
+                            if (!dst->touched[(size_t)q]) {
+                                launch_fill_zero(hostq, nq * (int64_t)din * 4, s);
+                                dst->touched[(size_t)q] = 1;
+                                E.d2h_bytes += nq * (int64_t)din * 4;
+                            }
+                            launch_scatter_add(dGA + (np + run[q]) * din, len, 0, 0, c->D.bnd_local + b0 + run[q],
+                                               hostq, din, s);
+                            GNN_HIP(hipEventRecord(dst->blk_direct[(size_t)q], s));
+                            dst->has_blk_direct[(size_t)q] = 1;
+                            ++E.direct_scatters;
+                            E.direct_scatter_bytes += 2 * len * (int64_t)din * 4;
+                            E.h2d_bytes += len * (int64_t)din * 4;
+                            E.d2h_bytes += len * (int64_t)din * 4;
+                            continue;
+                        }
                         int32_t gq;
                         if ((st = acquire(c, E, *dst, q, s, true, &gq)) != GNN_OK) return st;
                         launch_scatter_add(dGA + (np + run[q]) * din, len, 0, 0, c->D.bnd_local + b0 + run[q],
@@ -1219,6 +1277,8 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
     c->stream_stats.d2h_bytes = E.d2h_bytes;
     c->stream_stats.direct_gathers = E.direct_gathers;
     c->stream_stats.direct_bytes = E.direct_bytes;
+    c->stream_stats.direct_scatters = E.direct_scatters;
+    c->stream_stats.direct_scatter_bytes = E.direct_scatter_bytes;
     return check_launch(c, "gnn_epoch (streaming)");
 }
 

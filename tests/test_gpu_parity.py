@@ -374,6 +374,12 @@ def test_streaming_schedule_is_bit_identical_to_resident(case):
     if dtype == "f32":
         ref = og.epoch(cfg["model"], rowptr, colidx, dims, X, w, y, m)
         compare(r_a, ref, cfg["model"], tag=str(case))
+    stt = s.ctx.get_stream_stats()
+    say("  stream stats %s" % stt)
+    if factor <= 1.6:
+        # caches of two or three slots: rows of uncached blocks are gathered from, and gradient
+        # rows of uncached owner blocks added in, the pinned host arrays directly
+        assert stt["direct_gathers"] > 0 and stt["direct_scatters"] > 0
     with pytest.raises(GnnError) as e:
         s.ctx.gather_boundary(1, 0, s.stream)       # only gnn_epoch drives the streaming schedule
     assert e.value.status == 5
