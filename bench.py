@@ -374,7 +374,7 @@ def run_workload(name, args, steps, warmup, want_cpu):
                 else:
                     upper += (2 if l == 0 else 3) * (stats["nnz"] * (4 + dims[l] * es) + n * dims[l] * es)
             out["roofline"] = {
-                "kernel": "k_spmm_slots / k_spmm_items (aggregation over T_p and T_p^T: forward, recompute, "
+                "kernel": "k_spmm_slots / k_spmm_short / k_spmm_items (aggregation over T_p and T_p^T: forward, recompute, "
                           "transposed; column-sliced variant where rows are whole 128-byte lines)",
                 "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": source,

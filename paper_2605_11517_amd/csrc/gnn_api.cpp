@@ -222,7 +222,8 @@ void run_spmm_fwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, hipS
     const HostMeta& M = c->M;
     const int64_t r0 = M.off[(size_t)p], np = M.off[(size_t)p + 1] - r0;
     const int32_t din = c->dims[(size_t)layer - 1];
-    const SpmmItems items = plan_items(M.plan_fwd, c->D.fwd, p);
+    SpmmItems items = plan_items(M.plan_fwd, c->D.fwd, p);
+    items.avg_len = (float)(M.rp[(size_t)M.off[(size_t)p + 1]] - M.rp[(size_t)r0]) / (float)std::max<int64_t>(1, np);
     const float* rscale = c->D.rscale ? c->D.rscale + r0 : nullptr;
     void* Z = c->scratch + c->z_off();
     float* segpart = (float*)(c->scratch + c->ws.segpart);
@@ -457,7 +458,8 @@ const char* compute_bwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own
             else launch_gemm_nt((const float*)dY, dout, (const float*)W, dout, (float*)dZ, din, np, din, dout, ep, s);
         }
         const int64_t t0 = M.toff[(size_t)p];
-        const SpmmItems items = plan_items(M.plan_bwd, c->D.bwd, p);
+        SpmmItems items = plan_items(M.plan_bwd, c->D.bwd, p);
+        items.avg_len = (float)(M.trp[(size_t)M.toff[(size_t)p + 1]] - M.trp[(size_t)t0]) / (float)std::max<int64_t>(1, np + nb);
         float* segpart = (float*)(c->scratch + c->ws.segpart);
         // With fused_gprev the transposed aggregation adds each row of the gathered-row gradient
         // straight onto its owner row of grad A^{l-1} (own rows in place, boundary rows through
@@ -538,7 +540,8 @@ void xf_aggregate_fwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, 
     const HostMeta& M = c->M;
     const int64_t r0 = M.off[(size_t)p], np = M.off[(size_t)p + 1] - r0;
     const int32_t din = c->dims[(size_t)layer - 1], dout = c->dims[(size_t)layer], dp = c->padded(layer);
-    const SpmmItems items = plan_items(M.plan_fwd, c->D.fwd, p);
+    SpmmItems items = plan_items(M.plan_fwd, c->D.fwd, p);
+    items.avg_len = (float)(M.rp[(size_t)M.off[(size_t)p + 1]] - M.rp[(size_t)r0]) / (float)std::max<int64_t>(1, np);
     const float* rscale = c->D.rscale ? c->D.rscale + r0 : nullptr;
     float* Z = (float*)(c->scratch + c->ws.z);
     float* segpart = (float*)(c->scratch + c->ws.segpart);
@@ -638,7 +641,8 @@ void xf_aggregate_bwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own_c
                 compute_bwd_self(c, layer, p, (const char*)dYbuf, gprev_own, s, 0);
         }
         const int64_t t0b = M.toff[(size_t)p];
-        const SpmmItems itb = plan_items(M.plan_bwd, c->D.bwd, p);
+        SpmmItems itb = plan_items(M.plan_bwd, c->D.bwd, p);
+        itb.avg_len = (float)(M.trp[(size_t)M.toff[(size_t)p + 1]] - M.trp[(size_t)t0b]) / (float)std::max<int64_t>(1, np + nb);
         float* segb = (float*)(c->scratch + c->ws.segpart);
         SpmmScatter scb;
         scb.n_own = np;
@@ -698,7 +702,8 @@ void xf_aggregate_bwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own_c
         }
     }
     const int64_t t0 = M.toff[(size_t)p];
-    const SpmmItems items = plan_items(M.plan_bwd, c->D.bwd, p);
+    SpmmItems items = plan_items(M.plan_bwd, c->D.bwd, p);
+    items.avg_len = (float)(M.trp[(size_t)M.toff[(size_t)p + 1]] - M.trp[(size_t)t0]) / (float)std::max<int64_t>(1, np + nb);
     float* segpart = (float*)(c->scratch + c->ws.segpart);
     SpmmScatter sc;
     sc.n_own = np;

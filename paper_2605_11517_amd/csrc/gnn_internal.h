@@ -104,6 +104,7 @@ struct SpmmItems {
     int64_t nlong = 0;
     const int32_t* rows_sorted = nullptr;  // short rows, longest first (column-sliced kernel)
     int64_t nshort = 0;
+    float avg_len = 0.f;                   // entries per row of this operator block (0: not known)
 };
 // Optional fused scatter-accumulate for fp32 outputs: instead of out[r,:] = value, the kernel
 // does out[map(r),:] += value with map(r) = base_row + r for r < n_own and idx[r - n_own]
