@@ -200,7 +200,9 @@ def run_workload(name, args, steps, warmup, want_cpu):
         budget = int(n * (sum(dims) + sum(dims[1:])) * 4 * 0.56)
     s = Session(model, dims, rowptr, colidx, cfg["k"], cfg["part"], cfg["seed"], X, w, y, m,
                 dtype=cfg["dtype"], hbm_budget_bytes=budget,
-                layer_order=args.layer_order, progress=lambda msg: log("  " + msg))
+                layer_order=args.layer_order, fuse_gather=not args.staged_gather,
+                progress=lambda msg: log("  " + msg))
+    gather_fused = s.ctx.gather_is_fused()
     xf = [s.ctx.layer_is_transform_first(l) for l in range(1, len(dims))]
     # gnn_epoch runs a transform-first layer's contractions beside the aggregate-first layer below it
     overlapped = (cfg["dtype"] != "bf16" and model != "gat" and not budget and
@@ -274,8 +276,35 @@ def run_workload(name, args, steps, warmup, want_cpu):
 
     # the same epoch with every layer in the paper's order (aggregate, then transform; regather
     # and recompute in the backward pass of every layer): context, not the headline
-    paper_ms = None
-    if args.layer_order == "auto" and any(xf) and not args.no_paper_order and model != "gat" and not args.train:
+    # and with the gather as a step of its own, through the staging buffer
+    paper_ms, paper_gather = None, None
+    if ((args.layer_order == "auto" and any(xf)) or gather_fused) and not args.no_paper_order and \
+            model != "gat" and not args.train and not budget:
+        if any(xf):
+            s.set_layer_order("aggregate")
+        s.set_gather_fusion(False)
+        for i in range(min(warmup, 1)):
+            s.epoch()
+        torch.cuda.synchronize()
+        t3 = time.perf_counter()
+        reps = max(1, min(steps, 3))
+        for i in range(reps):
+            s.epoch()
+        torch.cuda.synchronize()
+        paper_ms = (time.perf_counter() - t3) / reps * 1e3
+        log("[%s] every layer aggregate-first, gather through staging: epoch %.2f ms" % (name, paper_ms))
+        if not args.no_profile:
+            s.ctx.set_profiling(1)
+            s.epoch()
+            torch.cuda.synchronize()
+            g_ms, g_launches = s.ctx.get_profile()["gather"]
+            s.ctx.set_profiling(0)
+            g_bytes = algorithmic_bytes(stats, dims, model, stats["k"], es, fused_scatter=True)["gather"]
+            if g_ms > 0:
+                paper_gather = {"ms_per_epoch": g_ms, "launches_per_epoch": g_launches,
+                                "algorithmic_GBps": g_bytes / (g_ms * 1e-3) / 1e9,
+                                "frac_hbm_peak": g_bytes / (g_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    elif args.layer_order == "auto" and any(xf) and not args.no_paper_order and model != "gat" and not args.train:
         s.set_layer_order("aggregate")
         for i in range(min(warmup, 1)):
             s.epoch()
@@ -306,15 +335,21 @@ def run_workload(name, args, steps, warmup, want_cpu):
                    "dims": list(dims), "k": stats["k"], "partitioner": cfg["part"],
                    "alpha": stats["sum_required"] / n, "sum_boundary": stats["sum_boundary"],
                    "layer_order": ["transform-first" if t else "aggregate-first" for t in xf],
+                   "gather": ("fused into the aggregation (rows read from the whole-graph array through B_p)"
+                              if gather_fused else "a step of its own, through the staging buffer"),
                    "side_stream_overlap": overlapped,
                    "setup_s": setup_s},
         "loss": loss,
     }
     if paper_ms is not None:
         out["ms_per_step_paper_order"] = paper_ms
+        if paper_gather is not None:
+            out["paper_order_gather"] = paper_gather
     if prof:
         ab = algorithmic_bytes(stats, dims, model, stats["k"], es,
                                fused_scatter=prof.get("scatter", (0, 0))[1] == 0, xf=xf)
+        if gather_fused:
+            ab["gather"] = 0                    # no staging copy is made
         fused = fused_layers(dims, xf, cfg["dtype"]) if model != "gat" else []
         fl = gemm_flops(stats, dims, model, fused)
         out["config"]["forward_fused_with_aggregation"] = [l + 1 for l in fused]
@@ -427,6 +462,9 @@ def main():
     ap.add_argument("--layer-order", choices=["auto", "aggregate"], default="auto",
                     help="auto: layers that narrow transform first (same results up to rounding, "
                          "fewer bytes); aggregate: every layer aggregates first, as in the paper")
+    ap.add_argument("--staged-gather", action="store_true",
+                    help="keep the gather a step of its own (staging buffer) instead of fusing it into the "
+                         "aggregation kernels")
     ap.add_argument("--no-paper-order", action="store_true",
                     help="skip the extra epochs that time the paper's layer order (ms_per_step_paper_order)")
     ap.add_argument("--hbm-budget-gb", type=float, default=0.0,

@@ -87,6 +87,8 @@ def load_library():
         "gnn_permute_rows": [vp, vp, vp, i64, i32, vp],
         "gnn_to_bf16": [vp, vp, vp, i64, vp],
         "gnn_gather_boundary": [vp, i32, i32, vp],
+        "gnn_set_gather_fusion": [vp, i32],
+        "gnn_gather_is_fused": [vp, P(i32)],
         "gnn_layer_fwd": [vp, i32, i32, vp],
         "gnn_loss": [vp, vp],
         "gnn_loss_static": [vp, vp, vp],
@@ -232,6 +234,14 @@ class Context:
     def gather_boundary(self, layer, p, stream):
         self._check(self.lib.gnn_gather_boundary(self.h, int(layer), int(p), stream))
 
+    def set_gather_fusion(self, on):
+        self._check(self.lib.gnn_set_gather_fusion(self.h, 1 if on else 0))
+
+    def gather_is_fused(self):
+        out = C.c_int32()
+        self._check(self.lib.gnn_gather_is_fused(self.h, C.byref(out)))
+        return bool(out.value)
+
     def layer_fwd(self, layer, p, stream):
         self._check(self.lib.gnn_layer_fwd(self.h, int(layer), int(p), stream))
 
@@ -311,7 +321,7 @@ class Session:
 
     def __init__(self, model, dims, rowptr, colidx, k, part_mode, seed, X, weights, labels,
                  train_mask, has_bias=True, user_part=None, device="cuda:0", dtype="f32",
-                 hbm_budget_bytes=0, layer_order="aggregate", progress=None):
+                 hbm_budget_bytes=0, layer_order="aggregate", fuse_gather=False, progress=None):
         import torch
         self.torch = torch
         if not torch.cuda.is_available():
@@ -325,6 +335,7 @@ class Session:
         self.ctx = Context(model, dims, dtype=GNN_BF16 if self.bf16 else GNN_F32, has_bias=has_bias,
                            hbm_budget_bytes=hbm_budget_bytes)
         self.ctx.set_layer_order(layer_order)
+        self.ctx.set_gather_fusion(fuse_gather)
         say = progress or (lambda msg: None)
         self.ctx.build_partitions(rowptr, colidx, k, part_mode, seed, user_part)
         say("partitions built")
@@ -434,6 +445,11 @@ class Session:
                       [ptr(w) for w in self.w], [ptr(g) for g in self.gw], ptr(self.labels),
                       ptr(self.mask), ptr(self.staging), ptr(self.scratch))
         t.cuda.synchronize()
+
+    def set_gather_fusion(self, on):
+        """Aggregation kernels read the boundary rows themselves (True) or from staging (False)."""
+        self.torch.cuda.synchronize()
+        self.ctx.set_gather_fusion(on)
 
     def epoch(self):
         return self.ctx.epoch(self.stream)

@@ -27,6 +27,7 @@ void free_device(DevMeta& D)
 {
     if (D.rp) (void)hipFree(D.rp);
     if (D.lcol) (void)hipFree(D.lcol);
+    if (D.gcol) (void)hipFree(D.gcol);
     if (D.ew) (void)hipFree(D.ew);
     if (D.rscale) (void)hipFree(D.rscale);
     if (D.bnd) (void)hipFree(D.bnd);
@@ -98,6 +99,33 @@ gnn_status ensure_device(gnn_ctx* c)
                        std::string("uploading partition metadata: ") + hipGetErrorString(e));
     }
     D.ready = true;
+    return GNN_OK;
+}
+
+// Column indices of every partition's operator as rows of the whole-graph arrays.
+gnn_status ensure_global_columns(gnn_ctx* c)
+{
+    if (c->D.gcol || c->M.lcol.empty()) return GNN_OK;
+    const HostMeta& M = c->M;
+    hipError_t e = hipMalloc((void**)&c->D.gcol, M.lcol.size() * sizeof(int32_t));
+    if (e != hipSuccess) {
+        c->D.gcol = nullptr;
+        (void)hipGetLastError();
+        return c->fail(e == hipErrorOutOfMemory ? GNN_ENOMEM : GNN_EHIP,
+                       std::string("global column indices: ") + hipGetErrorString(e));
+    }
+    for (int32_t p = 0; p < M.k; ++p) {
+        const int64_t r0 = M.off[(size_t)p], r1 = M.off[(size_t)p + 1];
+        const int64_t e0 = M.rp[(size_t)r0], e1 = M.rp[(size_t)r1];
+        launch_global_columns(c->D.lcol + e0, c->D.gcol + e0, e1 - e0, r1 - r0, r0, c->D.bnd + M.boff[(size_t)p], nullptr);
+    }
+    e = hipDeviceSynchronize();
+    if (e == hipSuccess) e = hipGetLastError();
+    if (e != hipSuccess) {
+        (void)hipFree(c->D.gcol);
+        c->D.gcol = nullptr;
+        return c->fail(GNN_EHIP, std::string("global column indices: ") + hipGetErrorString(e));
+    }
     return GNN_OK;
 }
 
@@ -230,8 +258,12 @@ void run_spmm_fwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, hipS
     const int b16 = c->bf16() ? 1 : 0;
     {
         Timed t(c, s, GNN_K_SPMM);
-        launch_spmm(c->D.rp + r0, c->D.lcol, c->D.ew, rscale, in_own, np, c->staging, Z, np, din, b16,
-                    b16, items, segpart, 1, SpmmScatter{}, s);
+        if (c->gather_fused())
+            launch_spmm(c->D.rp + r0, c->D.gcol, c->D.ew, rscale, c->layer_input(layer), M.n, nullptr, Z, np, din,
+                        b16, b16, items, segpart, 1, SpmmScatter{}, s);
+        else
+            launch_spmm(c->D.rp + r0, c->D.lcol, c->D.ew, rscale, in_own, np, c->staging, Z, np, din, b16,
+                        b16, items, segpart, 1, SpmmScatter{}, s);
     }
     if (items.nlong > 0) {
         Timed t(c, s, GNN_K_SPMM_REDUCE);
@@ -306,7 +338,7 @@ void compute_fwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, char*
     if (!c->bf16()) {
         // aggregate and transform in one kernel, the aggregated rows staying in LDS
         const SpmmItems items = plan_items(M.plan_fwd, c->D.fwd, p);
-        if (spmm_gemm_fused_ok(din, dout, items)) {
+        if (!c->gather_fused() && spmm_gemm_fused_ok(din, dout, items)) {
             const int64_t r0 = M.off[(size_t)p];
             const bool sage = c->model == GNN_SAGE_MEAN;
             const float* rscale = c->D.rscale ? c->D.rscale + r0 : nullptr;
@@ -562,8 +594,12 @@ void xf_aggregate_fwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, 
     const int agg_out_bf16 = direct && b16 && layer < c->L ? 1 : 0;
     {
         Timed t(c, s, GNN_K_SPMM);
-        launch_spmm(c->D.rp + r0, c->D.lcol, c->D.ew, rscale, H, np, c->staging, agg_out, np, dp, b16 ? 1 : 0,
-                    agg_out_bf16, items, segpart, 1, fin, s);
+        if (c->gather_fused())
+            launch_spmm(c->D.rp + r0, c->D.gcol, c->D.ew, rscale, c->hbuf, M.n, nullptr, agg_out, np, dp,
+                        b16 ? 1 : 0, agg_out_bf16, items, segpart, 1, fin, s);
+        else
+            launch_spmm(c->D.rp + r0, c->D.lcol, c->D.ew, rscale, H, np, c->staging, agg_out, np, dp, b16 ? 1 : 0,
+                        agg_out_bf16, items, segpart, 1, fin, s);
     }
     if (items.nlong > 0) {
         Timed t(c, s, GNN_K_SPMM_REDUCE);
@@ -1019,6 +1055,7 @@ gnn_status gnn_bind(gnn_ctx* c, const void* feat, void* const* act, void* const*
                                    "scratch must be 16-byte aligned");
     gnn_status st = ensure_device(c);
     if (st != GNN_OK) return st;
+    if (c->fuse_gather && !c->streaming() && c->model != GNN_GAT && (st = ensure_global_columns(c)) != GNN_OK) return st;
     c->feat = (const char*)feat;
     c->act.assign((size_t)L, nullptr);
     c->gact.assign((size_t)L, nullptr);
@@ -1103,9 +1140,11 @@ gnn_status gnn_gather_boundary(gnn_ctx* c, int32_t layer, int32_t p, void* strea
             c->staged_p = p;
             return check_launch(c, "gnn_gather_boundary");
         }
-        Timed t(c, s, GNN_K_GATHER);
-        launch_gather_rows(c->hbuf, c->D.bnd + b0, c->staging, nb, (int64_t)c->padded(layer) * c->es(), s);
-    } else {
+        if (!c->gather_fused()) {
+            Timed t(c, s, GNN_K_GATHER);
+            launch_gather_rows(c->hbuf, c->D.bnd + b0, c->staging, nb, (int64_t)c->padded(layer) * c->es(), s);
+        }
+    } else if (!c->gather_fused()) {
         const int64_t row_bytes = (int64_t)c->dims[(size_t)layer - 1] * c->es();
         Timed t(c, s, GNN_K_GATHER);
         launch_gather_rows(c->layer_input(layer), c->D.bnd + b0, c->staging, nb, row_bytes, s);
@@ -1113,6 +1152,24 @@ gnn_status gnn_gather_boundary(gnn_ctx* c, int32_t layer, int32_t p, void* strea
     c->staged_layer = layer;
     c->staged_p = p;
     return check_launch(c, "gnn_gather_boundary");
+}
+
+gnn_status gnn_set_gather_fusion(gnn_ctx* c, int32_t on)
+{
+    if (!c) return GNN_EINVAL;
+    if (on != 0 && on != 1) return c->fail(GNN_EINVAL, "gnn_set_gather_fusion takes 0 or 1");
+    c->fuse_gather = on == 1;
+    c->staged_layer = c->staged_p = -1;       // staging holds nothing the other mode could use
+    if (c->fuse_gather && c->D.ready && !c->streaming() && c->model != GNN_GAT) return ensure_global_columns(c);
+    return GNN_OK;
+}
+
+gnn_status gnn_gather_is_fused(const gnn_ctx* c, int32_t* out)
+{
+    if (!c || !out) return GNN_EINVAL;
+    // the index array is set up by gnn_bind at the latest
+    *out = c->fuse_gather && !c->streaming() && c->model != GNN_GAT ? 1 : 0;
+    return GNN_OK;
 }
 
 gnn_status gnn_layer_fwd(gnn_ctx* c, int32_t layer, int32_t p, void* stream)

@@ -14,6 +14,7 @@ namespace gnnmi {
 struct DevMeta {
     int64_t* rp = nullptr;
     int32_t* lcol = nullptr;
+    int32_t* gcol = nullptr;   // the same entries as rows of the whole-graph arrays (fused gather)
     float* ew = nullptr;
     float* rscale = nullptr;
     int32_t* bnd = nullptr;
@@ -119,6 +120,10 @@ struct gnn_ctx {
         // width, and regathers nothing.
         return 2 * dout < din * (layer >= 2 ? 3 : 2);
     }
+    // Resident schedule: the aggregation reads the boundary rows A^{l-1}[B_p[i]] itself, through
+    // column indices that name rows of the whole-graph array, and no staging copy is made
+    bool fuse_gather = false;
+    bool gather_fused() const { return fuse_gather && !streaming() && model != GNN_GAT && D.gcol != nullptr; }
     bool stream_xf_ok = false;               // set by update_stream_xf() once the partitions exist
     // bytes of the whole-graph buffers the transform-first layers (by the cost rule) would need
     int64_t xf_buffer_bytes(int64_t n) const

@@ -238,6 +238,9 @@ hipError_t launch_loss_static(const float* logits, const int32_t* labels, const 
                               hipStream_t s);
 
 void launch_fill_zero(void* p, int64_t bytes, hipStream_t s);
+// gcol[e] = lcol[e] < n_own ? base + lcol[e] : bnd[lcol[e] - n_own] for e in [0, count)
+void launch_global_columns(const int32_t* lcol, int32_t* gcol, int64_t count, int64_t n_own, int64_t base,
+                           const int32_t* bnd, hipStream_t s);
 
 // ---- graph attention (kernels_gat.hip) ----------------------------------------------------
 // Rows of one partition for the row-wise attention passes: rp points at the partition's first

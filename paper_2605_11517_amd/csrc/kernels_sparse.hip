@@ -992,6 +992,19 @@ __global__ __launch_bounds__(kBlock) void k_scatter_add(const float* __restrict_
     }
 }
 
+// gcol[e] = row of the whole-graph array that local column lcol[e] of partition p stands for:
+// own rows follow each other from `base`, the others are listed in the boundary list
+__global__ __launch_bounds__(kBlock) void k_global_columns(const int32_t* __restrict__ lcol,
+                                                           int32_t* __restrict__ gcol, int64_t count,
+                                                           int32_t n_own, int32_t base,
+                                                           const int32_t* __restrict__ bnd)
+{
+    for (int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x; e < count; e += (int64_t)gridDim.x * kBlock) {
+        const int32_t c = lcol[e];
+        gcol[e] = c < n_own ? base + c : bnd[c - n_own];
+    }
+}
+
 __global__ __launch_bounds__(kBlock) void k_fill_zero(uint4* __restrict__ p, int64_t n16,
                                                       uint8_t* __restrict__ tail, int ntail)
 {
@@ -1017,10 +1030,15 @@ void launch_scatter_rows(const void* src, const int32_t* idx, void* dst, int64_t
 
 namespace {
 
-inline float short_fwd_max_s()
+// Operators whose rows average fewer entries than this take k_spmm_short.  The choice looks at the
+// operator only, never at where its source rows lie, so that one operator is summed by the same
+// kernel (in the same order) whether its sources are one array or two.
+inline float short_rows_max()
 {
     static const float v = [] {
-        const char* e = std::getenv("GNNMI_SPMM_SHORT_FWD");
+        const char* off = std::getenv("GNNMI_SPMM_SHORT");
+        if (off && off[0] == '0') return 0.f;
+        const char* e = std::getenv("GNNMI_SPMM_SHORT_MAX");
         return e ? (float)std::atof(e) : 32.f;
     }();
     return v;
@@ -1062,7 +1080,7 @@ void spmm_typed(const int64_t* rp, const int32_t* col, const float* w, const flo
             g.map_n_own = -1; g.map_base = 0; g.map_idx = nullptr;
             g.bias = sc.bias; g.relu = sc.relu;
             const dim3 grid((unsigned)(blocks * ns));
-            const bool few2s = b_rows != nullptr && items.avg_len > 0.f && items.avg_len < short_fwd_max_s();
+            const bool few2s = items.avg_len > 0.f && items.avg_len < short_rows_max();
             if (G == 16 && few2s) hipLaunchKernelGGL((k_spmm_short<TIn, TOut, 16, 4, 1, false>), grid, dim3(kBlock), 0, s, g, ns);
             else if (G == 16) hipLaunchKernelGGL((k_spmm_slots<TIn, TOut, 16>), grid, dim3(kBlock), 0, s, g, ns);
             else if (few2s) hipLaunchKernelGGL((k_spmm_short<TIn, TOut, 32, 4, 1, false>), grid, dim3(kBlock), 0, s, g, ns);
@@ -1079,24 +1097,15 @@ void spmm_typed(const int64_t* rp, const int32_t* col, const float* w, const flo
         return !(e && e[0] == '0');
     }();
     const int nvec = (d + EPV - 1) / EPV;
-    static const bool short_rows_variant = [] {
-        const char* e = std::getenv("GNNMI_SPMM_SHORT");
-        return !(e && e[0] == '0');
-    }();
-    // operators whose rows average fewer than two dozen entries and whose sources are one array
-    // (the transposed operator of a partition): the variant with four loads in flight per slot,
-    // 32-bit source offsets and a rolled loop - 51 registers, eight wavefronts per SIMD.  Measured:
-    // 315 -> 264 ms of transposed aggregation per epoch at 3 entries per row, 20.3 -> 18.4 ms at 12.
-    static const float short_max = [] {
-        const char* e = std::getenv("GNNMI_SPMM_SHORT_MAX");
-        return e ? (float)std::atof(e) : 24.f;
-    }();
-    const bool few = short_rows_variant && items.avg_len > 0.f && items.avg_len < short_max && b_rows == nullptr &&
-                     n_a * (int64_t)d < ((int64_t)1 << 32);
-    // two-source operators (own rows + gathered rows) with short rows take the same variant with
-    // 64-bit offsets: 3 % of the forward aggregation at 17 entries per row, nothing at 55
-    const float short_fwd_max = short_fwd_max_s();
-    const bool few2 = !few && b_rows != nullptr && items.avg_len > 0.f && items.avg_len < short_fwd_max;
+    // Operators with short rows (the transposed operators R_p: 3 to 27 entries per row on the
+    // bench workloads; the forward operators of sparse directed graphs: 17) take the variant with
+    // four loads in flight per slot and a rolled loop: 51-57 registers, eight wavefronts per SIMD.
+    // Measured: 315 -> 264 ms of transposed aggregation per epoch at 3.6 entries per row, 20.3 ->
+    // 18.4 ms at 12; forward 3 % at 17 entries per row, nothing at 55.  `few`: one source array of
+    // fewer than 2^32 elements, 32-bit offsets; `few2`: 64-bit addresses.
+    const bool short_rows = items.avg_len > 0.f && items.avg_len < short_rows_max();
+    const bool few = short_rows && b_rows == nullptr && n_a * (int64_t)d < ((int64_t)1 << 32);
+    const bool few2 = short_rows && !few;
     if (use_narrow && vec && (few || few2) && nvec > 32 && nvec <= 64 && items.rows_sorted && sizeof(TIn) == 4 &&
         (sc.n_own < 0 || sizeof(TOut) == 4) && items.nsegs + items.nshort > 0) {
         // rows of 33..64 vectors: two vectors per lane, two rows per wavefront
@@ -1127,6 +1136,7 @@ void spmm_typed(const int64_t* rp, const int32_t* col, const float* w, const flo
         const dim3 grid1((unsigned)blocks);
         if (G == 4) hipLaunchKernelGGL((k_spmm_slots<TIn, TOut, 4>), grid1, dim3(kBlock), 0, s, g, 1);
         else if (G == 8 && few) hipLaunchKernelGGL((k_spmm_short<TIn, TOut, 8, 4, 1>), grid1, dim3(kBlock), 0, s, g, 1);
+        else if (G == 8 && few2) hipLaunchKernelGGL((k_spmm_short<TIn, TOut, 8, 4, 1, false>), grid1, dim3(kBlock), 0, s, g, 1);
         else if (G == 8) hipLaunchKernelGGL((k_spmm_slots<TIn, TOut, 8>), grid1, dim3(kBlock), 0, s, g, 1);
         else if (G == 16 && few) hipLaunchKernelGGL((k_spmm_short<TIn, TOut, 16, 4, 1>), grid1, dim3(kBlock), 0, s, g, 1);
         else if (G == 16 && few2) hipLaunchKernelGGL((k_spmm_short<TIn, TOut, 16, 4, 1, false>), grid1, dim3(kBlock), 0, s, g, 1);
@@ -1287,6 +1297,15 @@ void launch_scatter_add(const float* src, int64_t nrows, int64_t n_own, int64_t 
     else
         hipLaunchKernelGGL((k_scatter_add<false>), dim3((unsigned)blocks), dim3(kBlock), 0, s, src,
                            nrows, n_own, base_row, idx, dst, d, vpr);
+}
+
+void launch_global_columns(const int32_t* lcol, int32_t* gcol, int64_t count, int64_t n_own, int64_t base,
+                           const int32_t* bnd, hipStream_t s)
+{
+    if (count <= 0) return;
+    const int64_t blocks = std::min<int64_t>((count + kBlock - 1) / kBlock, 8192);
+    hipLaunchKernelGGL(k_global_columns, dim3((unsigned)blocks), dim3(kBlock), 0, s, lcol, gcol, count,
+                       (int32_t)n_own, (int32_t)base, bnd);
 }
 
 void launch_fill_zero(void* p, int64_t bytes, hipStream_t s)

@@ -120,6 +120,73 @@ def test_gathered_rows_are_bit_exact(name):
                 assert rel_err(staged, ref["act"][layer - 2][b]) <= TOL
 
 
+FUSED_GATHER = [
+    # (model, dims, n, m_draw, symmetric, k, mode, dtype, layer order)
+    ("gcn", (64, 64, 16), 10000, 100000, True, 4, "random", "f32", "aggregate"),
+    ("sage", (100, 256, 256, 47), 3000, 40000, True, 5, "lp", "f32", "aggregate"),
+    ("sage", (100, 256, 256, 47), 3000, 40000, True, 5, "lp", "f32", "auto"),       # H is gathered
+    ("gcn", (128, 128, 128, 172), 4000, 50000, False, 7, "lp", "f32", "auto"),      # directed: short rows
+    ("gcn", (7, 9, 5), 300, 1500, True, 3, "random", "f32", "aggregate"),           # scalar loads
+    ("sage", (1028, 16, 4), 200, 1500, True, 2, "random", "f32", "auto"),           # rows of 1028 floats
+    ("gcn", (36, 40, 8), 2500, 90000, True, 3, "lp", "f32", "aggregate"),           # hubs cut into segments
+    ("gcn", (64, 128, 64, 16), 3000, 30000, True, 4, "lp", "bf16", "auto"),
+    ("sage", (72, 136, 8), 2000, 16000, True, 3, "random", "bf16", "aggregate"),
+    ("gcn", (64, 32, 8), 500, 4000, True, 1, "random", "f32", "aggregate"),         # k = 1: no boundary
+]
+
+
+@pytest.mark.parametrize("case", FUSED_GATHER,
+                         ids=lambda c: "%s-%s-k%d-%s-%s" % (c[0], "x".join(map(str, c[1])), c[5], c[7], c[8]))
+def test_gather_fused_into_the_aggregation_gives_the_staged_bits(case):
+    """gnn_set_gather_fusion(1): the aggregation kernels read row B_p[i] of the whole-graph array
+    where they read row i of staging before.  Same terms in the same order, so loss, activations
+    and every gradient must be the staged epoch's bits (which the other tests hold against the
+    oracle; the fp32 cases are held against it here as well), and staging must stay untouched."""
+    model, dims, n, m_draw, sym, k, mode, dtype, order = case
+    say("case fused gather %s" % (case,))
+    import torch
+    from paper_2605_11517_amd import Session
+    from synth import to_bf16_grid
+    rowptr, colidx = small_graph(n, m_draw, seed=61, symmetric=sym, self_loops=(model == "gcn"))
+    cfg = dict(model=model, dims=dims, seed=21, train_frac=0.5)
+    X, y, m, w = make_inputs(cfg, n)
+    if dtype == "bf16":
+        X = to_bf16_grid(X)
+        for layer in w:
+            layer["W"] = to_bf16_grid(layer["W"])
+            if layer["Ws"] is not None:
+                layer["Ws"] = to_bf16_grid(layer["Ws"])
+    s = Session(model, dims, rowptr, colidx, k, mode, 3, X, w, y, m, dtype=dtype, layer_order=order)
+    assert not s.ctx.gather_is_fused()
+    loss0 = s.epoch()
+    staged = s.results()
+    s.set_gather_fusion(True)
+    assert s.ctx.gather_is_fused()
+    s.staging.fill_(0xFF)                       # NaN patterns: a read of staging would show
+    for a in s.act + s.gact:
+        a.zero_()
+    loss1 = s.epoch()
+    fused = s.results()
+    assert loss1 == loss0
+    for key in ("act", "gact", "gW", "gWs", "gb"):
+        for l, (a, b) in enumerate(zip(fused[key], staged[key])):
+            if a is None:
+                assert b is None
+                continue
+            assert np.array_equal(a.view(np.uint32), b.view(np.uint32)), (key, l)
+    assert bool((s.staging == 0xFF).all()), "staging was written although the gather is fused"
+    if dtype == "f32":
+        # (pre-activations within rounding distance of zero: the oracle takes the path's decision)
+        fwd = og.forward(model, rowptr, colidx, dims, X, w)
+        ref = aligned_backward(og, fwd, fused["act"], w, X, y, m, TOL)
+        assert abs(loss1 - ref["loss"]) <= TOL * abs(ref["loss"])
+        compare(fused, ref, model, tag="fused gather")
+    # and back: the staged path fills staging again
+    s.set_gather_fusion(False)
+    assert s.epoch() == loss0
+    assert not bool((s.staging == 0xFF).all()) or k == 1
+
+
 def test_two_epochs_are_bit_identical_and_stepping_by_hand_equals_epoch():
     say("case determinism + hand stepping")
     import torch
