@@ -39,12 +39,16 @@ def padded_width(d):
     return (d + 3) // 4 * 4
 
 
-def algorithmic_bytes(stats, dims, model, n_parts, es=4, fused_scatter=False, xf=None, pad=padded_width):
+def algorithmic_bytes(stats, dims, model, n_parts, es=4, fused_scatter=False, xf=None, pad=padded_width,
+                      masked=None):
     """HBM bytes the method has to move per epoch, by kernel class (lower bound: every needed
     source row is read once per partition).  es = bytes per stored activation (4 fp32, 2 bf16);
     gradients of activations are always fp32.  xf[l-1]: layer l transforms first, so it
     gathers, aggregates and scatter-accumulates rows of its (padded) output width, once
-    forward and once backward, with no regather and no recompute."""
+    forward and once backward, with no regather and no recompute.  masked = (entries, rows,
+    train vertices) of the output layer's transposed operator over train vertices, when in use:
+    that pass then reads only those entries and the gradient rows of train vertices, and adds
+    onto `rows` rows."""
     n, nnz, k = stats["n"], stats["nnz"], stats["k"]
     sum_r = n + stats["sum_boundary"]            # sum over partitions of |own_p| + |B_p|
     sum_b = stats["sum_boundary"]
@@ -63,7 +67,11 @@ def algorithmic_bytes(stats, dims, model, n_parts, es=4, fused_scatter=False, xf
             # products dY[v] . H[u] (same traffic as an aggregation, 4 bytes written per entry)
             out["gather"] += one_gather * (2 if model == "gat" else 1)
             out["spmm"] += one_spmm * (2 if model == "gat" else 1)
-            out["spmm_t"] += 8 * nnz + 8 * (sum_r + k) + n * hrow + 2 * sum_r * row + 4 * sum_b
+            if masked and l == L:
+                m_e, m_r, m_v = masked
+                out["spmm_t"] += 8 * m_e + 12 * (m_r + k) + m_v * hrow + 2 * m_r * row
+            else:
+                out["spmm_t"] += 8 * nnz + 8 * (sum_r + k) + n * hrow + 2 * sum_r * row + 4 * sum_b
             continue
         d = dims[l - 1]
         row = d * es
@@ -74,7 +82,10 @@ def algorithmic_bytes(stats, dims, model, n_parts, es=4, fused_scatter=False, xf
         spmm = per_entry * nnz + 8 * (n + k) + sum_r * row + n * row + (4 * n if model == "sage" else 0)
         out["spmm"] += 2 * spmm
         if l >= 2:
-            if fused_scatter:
+            if fused_scatter and masked and l == L:
+                m_e, m_r, m_v = masked
+                out["spmm_t"] += 8 * m_e + 12 * (m_r + k) + m_v * row + 2 * m_r * grow
+            elif fused_scatter:
                 # transposed aggregation adds its rows straight onto their owners: read dZ once,
                 # read-modify-write every required row of grad A^{l-1}
                 out["spmm_t"] += 8 * nnz + 8 * (sum_r + k) + n * row + 2 * sum_r * grow + 4 * sum_b
@@ -201,8 +212,10 @@ def run_workload(name, args, steps, warmup, want_cpu):
     s = Session(model, dims, rowptr, colidx, cfg["k"], cfg["part"], cfg["seed"], X, w, y, m,
                 dtype=cfg["dtype"], hbm_budget_bytes=budget,
                 layer_order=args.layer_order, fuse_gather=not args.staged_gather,
-                progress=lambda msg: log("  " + msg))
+                masked_backward=not args.full_backward, progress=lambda msg: log("  " + msg))
     gather_fused = s.ctx.gather_is_fused()
+    m_entries, m_rows = s.ctx.masked_backward_size()
+    masked = (m_entries, m_rows, int((m != 0).sum())) if m_rows or m_entries else None
     xf = [s.ctx.layer_is_transform_first(l) for l in range(1, len(dims))]
     # gnn_epoch runs a transform-first layer's contractions beside the aggregate-first layer below it
     overlapped = (cfg["dtype"] != "bf16" and model != "gat" and not budget and
@@ -283,6 +296,7 @@ def run_workload(name, args, steps, warmup, want_cpu):
         if any(xf):
             s.set_layer_order("aggregate")
         s.set_gather_fusion(False)
+        s.set_masked_backward(False)
         for i in range(min(warmup, 1)):
             s.epoch()
         torch.cuda.synchronize()
@@ -337,6 +351,9 @@ def run_workload(name, args, steps, warmup, want_cpu):
                    "layer_order": ["transform-first" if t else "aggregate-first" for t in xf],
                    "gather": ("fused into the aggregation (rows read from the whole-graph array through B_p)"
                               if gather_fused else "a step of its own, through the staging buffer"),
+                   "output_layer_backward": ("%d operator entries of train vertices of %d (the loss gradient is "
+                                             "zero elsewhere)" % (masked[0], nnz) if masked
+                                             else "every operator entry"),
                    "side_stream_overlap": overlapped,
                    "setup_s": setup_s},
         "loss": loss,
@@ -347,7 +364,7 @@ def run_workload(name, args, steps, warmup, want_cpu):
             out["paper_order_gather"] = paper_gather
     if prof:
         ab = algorithmic_bytes(stats, dims, model, stats["k"], es,
-                               fused_scatter=prof.get("scatter", (0, 0))[1] == 0, xf=xf)
+                               fused_scatter=prof.get("scatter", (0, 0))[1] == 0, xf=xf, masked=masked)
         if gather_fused:
             ab["gather"] = 0                    # no staging copy is made
         fused = fused_layers(dims, xf, cfg["dtype"]) if model != "gat" else []
@@ -403,11 +420,16 @@ def run_workload(name, args, steps, warmup, want_cpu):
             L = len(dims) - 1
             upper = 0
             for l in range(L):
+                # the output layer's transposed pass over train vertices only reads that many rows
+                last_t = (masked[0], masked[1]) if masked and l == L - 1 else (stats["nnz"], n)
                 if xf[l]:
                     roww = padded_width(dims[l + 1]) * 4
-                    upper += (3 if model == "gat" else 2) * (stats["nnz"] * (4 + roww) + n * roww)
+                    upper += (2 if model == "gat" else 1) * (stats["nnz"] * (4 + roww) + n * roww)
+                    upper += last_t[0] * (4 + roww) + last_t[1] * roww
                 else:
-                    upper += (2 if l == 0 else 3) * (stats["nnz"] * (4 + dims[l] * es) + n * dims[l] * es)
+                    upper += 2 * (stats["nnz"] * (4 + dims[l] * es) + n * dims[l] * es)
+                    if l > 0:
+                        upper += last_t[0] * (4 + dims[l] * es) + last_t[1] * dims[l] * es
             out["roofline"] = {
                 "kernel": "k_spmm_slots / k_spmm_short / k_spmm_items (aggregation over T_p and T_p^T: forward, recompute, "
                           "transposed; column-sliced variant where rows are whole 128-byte lines)",
@@ -465,6 +487,9 @@ def main():
     ap.add_argument("--staged-gather", action="store_true",
                     help="keep the gather a step of its own (staging buffer) instead of fusing it into the "
                          "aggregation kernels")
+    ap.add_argument("--full-backward", action="store_true",
+                    help="output layer's transposed aggregation over every operator entry instead of those of "
+                         "train vertices only")
     ap.add_argument("--no-paper-order", action="store_true",
                     help="skip the extra epochs that time the paper's layer order (ms_per_step_paper_order)")
     ap.add_argument("--hbm-budget-gb", type=float, default=0.0,

@@ -249,6 +249,23 @@ gnn_status gnn_gather_boundary(gnn_ctx *ctx, int32_t layer, int32_t p, void *str
  * no effect with a streaming budget or GNN_GAT layers (gnn_gather_is_fused reports 0 there).
  * GNN_EINVAL for on outside {0, 1}, GNN_ENOMEM / GNN_EHIP if the index array cannot be set up. */
 gnn_status gnn_set_gather_fusion(gnn_ctx *ctx, int32_t on);
+/* Backward pass of the output layer over train vertices only (resident schedule, GNN_GCN and
+ * GNN_SAGE_MEAN).  The gradient of the loss is zero in every row outside train_mask, so the
+ * output layer's transposed aggregation (grad of the gathered rows, scatter-accumulated onto
+ * their owners) needs only the operator entries whose destination is a train vertex.  With
+ * on = 1, gnn_bind (or this call, on a bound context) copies train_mask to the host once and
+ * builds that sub-operator of every partition's transpose: kept entries in their original
+ * order, rows left without an entry dropped (about 12 bytes of device memory per kept entry).
+ * The entries left out multiply rows that are exactly zero, so results differ from on = 0
+ * only by the order in which the kept terms of a long row are added (rounding).  The caller
+ * promises not to change the contents of train_mask while the context is bound to it (bind
+ * again after changing it).  Default 0.  No effect with a streaming budget, with GNN_GAT, or
+ * when the scatter-accumulate is not fused into the aggregation.
+ * GNN_EINVAL for on outside {0, 1}; GNN_ENOMEM / GNN_EHIP if the sub-operator cannot be set up. */
+gnn_status gnn_set_masked_backward(gnn_ctx *ctx, int32_t on);
+/* Size of that sub-operator over all partitions: operator entries kept and rows of the gathered-row
+ * gradient that receive a sum; both 0 while it is not in use. */
+gnn_status gnn_get_masked_backward_size(const gnn_ctx *ctx, int64_t *entries, int64_t *rows);
 /* *out = 1 when the aggregation kernels of this context read the boundary rows themselves. */
 gnn_status gnn_gather_is_fused(const gnn_ctx *ctx, int32_t *out);
 

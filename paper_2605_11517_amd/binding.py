@@ -89,6 +89,8 @@ def load_library():
         "gnn_gather_boundary": [vp, i32, i32, vp],
         "gnn_set_gather_fusion": [vp, i32],
         "gnn_gather_is_fused": [vp, P(i32)],
+        "gnn_set_masked_backward": [vp, i32],
+        "gnn_get_masked_backward_size": [vp, P(i64), P(i64)],
         "gnn_layer_fwd": [vp, i32, i32, vp],
         "gnn_loss": [vp, vp],
         "gnn_loss_static": [vp, vp, vp],
@@ -237,6 +239,15 @@ class Context:
     def set_gather_fusion(self, on):
         self._check(self.lib.gnn_set_gather_fusion(self.h, 1 if on else 0))
 
+    def set_masked_backward(self, on):
+        self._check(self.lib.gnn_set_masked_backward(self.h, 1 if on else 0))
+
+    def masked_backward_size(self):
+        """(operator entries, result rows) of the train-vertex operator; (0, 0) when not in use."""
+        e, r = C.c_int64(), C.c_int64()
+        self._check(self.lib.gnn_get_masked_backward_size(self.h, C.byref(e), C.byref(r)))
+        return int(e.value), int(r.value)
+
     def gather_is_fused(self):
         out = C.c_int32()
         self._check(self.lib.gnn_gather_is_fused(self.h, C.byref(out)))
@@ -321,7 +332,8 @@ class Session:
 
     def __init__(self, model, dims, rowptr, colidx, k, part_mode, seed, X, weights, labels,
                  train_mask, has_bias=True, user_part=None, device="cuda:0", dtype="f32",
-                 hbm_budget_bytes=0, layer_order="aggregate", fuse_gather=False, progress=None):
+                 hbm_budget_bytes=0, layer_order="aggregate", fuse_gather=False, masked_backward=False,
+                 progress=None):
         import torch
         self.torch = torch
         if not torch.cuda.is_available():
@@ -336,6 +348,7 @@ class Session:
                            hbm_budget_bytes=hbm_budget_bytes)
         self.ctx.set_layer_order(layer_order)
         self.ctx.set_gather_fusion(fuse_gather)
+        self.ctx.set_masked_backward(masked_backward)
         say = progress or (lambda msg: None)
         self.ctx.build_partitions(rowptr, colidx, k, part_mode, seed, user_part)
         say("partitions built")
@@ -445,6 +458,11 @@ class Session:
                       [ptr(w) for w in self.w], [ptr(g) for g in self.gw], ptr(self.labels),
                       ptr(self.mask), ptr(self.staging), ptr(self.scratch))
         t.cuda.synchronize()
+
+    def set_masked_backward(self, on):
+        """Output layer's transposed aggregation over train vertices only (True) or over every entry."""
+        self.torch.cuda.synchronize()
+        self.ctx.set_masked_backward(on)
 
     def set_gather_fusion(self, on):
         """Aggregation kernels read the boundary rows themselves (True) or from staging (False)."""

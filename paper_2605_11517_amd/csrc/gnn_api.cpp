@@ -23,8 +23,32 @@ int64_t align_up(int64_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 namespace {
 
+void free_plan(DevMeta::Plan& P)
+{
+    if (P.range_rows) (void)hipFree(P.range_rows);
+    if (P.seg_row) (void)hipFree(P.seg_row);
+    if (P.seg_begin) (void)hipFree(P.seg_begin);
+    if (P.seg_len) (void)hipFree(P.seg_len);
+    if (P.long_row) (void)hipFree(P.long_row);
+    if (P.long_first) (void)hipFree(P.long_first);
+    if (P.long_nseg) (void)hipFree(P.long_nseg);
+    if (P.rows_sorted) (void)hipFree(P.rows_sorted);
+    P = DevMeta::Plan{};
+}
+
+void free_masked(DevMeta::Masked& T)
+{
+    if (T.trp) (void)hipFree(T.trp);
+    if (T.tcol) (void)hipFree(T.tcol);
+    if (T.tw) (void)hipFree(T.tw);
+    if (T.out_row) (void)hipFree(T.out_row);
+    free_plan(T.plan);
+    T = DevMeta::Masked{};
+}
+
 void free_device(DevMeta& D)
 {
+    free_masked(D.masked_t);
     if (D.rp) (void)hipFree(D.rp);
     if (D.lcol) (void)hipFree(D.lcol);
     if (D.gcol) (void)hipFree(D.gcol);
@@ -38,16 +62,8 @@ void free_device(DevMeta& D)
     if (D.tw) (void)hipFree(D.tw);
     if (D.order) (void)hipFree(D.order);
     if (D.tperm) (void)hipFree(D.tperm);
-    for (DevMeta::Plan* P : {&D.fwd, &D.bwd}) {
-        if (P->range_rows) (void)hipFree(P->range_rows);
-        if (P->seg_row) (void)hipFree(P->seg_row);
-        if (P->seg_begin) (void)hipFree(P->seg_begin);
-        if (P->seg_len) (void)hipFree(P->seg_len);
-        if (P->long_row) (void)hipFree(P->long_row);
-        if (P->long_first) (void)hipFree(P->long_first);
-        if (P->long_nseg) (void)hipFree(P->long_nseg);
-        if (P->rows_sorted) (void)hipFree(P->rows_sorted);
-    }
+    free_plan(D.fwd);
+    free_plan(D.bwd);
     D = DevMeta{};
 }
 
@@ -59,6 +75,62 @@ hipError_t upload(T*& dst, const std::vector<T>& src)
     hipError_t e = hipMalloc((void**)&dst, src.size() * sizeof(T));
     if (e != hipSuccess) return e;
     return hipMemcpy(dst, src.data(), src.size() * sizeof(T), hipMemcpyHostToDevice);
+}
+
+hipError_t upload_plan(DevMeta::Plan& P, const HostMeta::Plan& H)
+{
+    hipError_t e = hipSuccess;
+    auto step = [&](hipError_t r) { if (e == hipSuccess) e = r; };
+    step(upload(P.range_rows, H.range_rows));
+    step(upload(P.seg_row, H.seg_row));
+    step(upload(P.seg_begin, H.seg_begin));
+    step(upload(P.seg_len, H.seg_len));
+    step(upload(P.long_row, H.long_row));
+    step(upload(P.long_first, H.long_first));
+    step(upload(P.long_nseg, H.long_nseg));
+    step(upload(P.rows_sorted, H.rows_sorted));
+    return e;
+}
+
+// Reads the bound train mask and builds the output layer's transposed operator over train
+// vertices, on the host, then uploads it.
+gnn_status build_masked(gnn_ctx* c)
+{
+    free_masked(c->D.masked_t);
+    c->M.masked_t = HostMeta::MaskedTranspose{};
+    std::vector<uint8_t> mask((size_t)c->M.n);
+    hipError_t e = hipDeviceSynchronize();
+    if (e == hipSuccess) e = hipMemcpy(mask.data(), c->mask, mask.size(), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return c->fail(GNN_EHIP, std::string("reading the train mask: ") + hipGetErrorString(e));
+    }
+    try {
+        build_masked_transpose(c->M, mask.data());
+    } catch (const std::bad_alloc&) {
+        c->M.masked_t = HostMeta::MaskedTranspose{};
+        return c->fail(GNN_ENOMEM, "out of host memory while building the train-vertex operator");
+    }
+    const HostMeta::MaskedTranspose& H = c->M.masked_t;
+    DevMeta::Masked& T = c->D.masked_t;
+    auto step = [&](hipError_t r) { if (e == hipSuccess) e = r; };
+    step(upload(T.trp, H.trp));
+    step(upload(T.tcol, H.tcol));
+    step(upload(T.tw, H.tw));
+    step(upload(T.out_row, H.out_row));
+    step(upload_plan(T.plan, H.plan));
+    if (e != hipSuccess) {
+        free_masked(T);
+        (void)hipGetLastError();
+        return c->fail(e == hipErrorOutOfMemory ? GNN_ENOMEM : GNN_EHIP,
+                       std::string("uploading the train-vertex operator: ") + hipGetErrorString(e));
+    }
+    T.ready = true;
+    // the host copy of the entries is not needed again (the plan offsets are)
+    std::vector<int32_t>().swap(c->M.masked_t.tcol);
+    std::vector<float>().swap(c->M.masked_t.tw);
+    std::vector<int32_t>().swap(c->M.masked_t.out_row);
+    return GNN_OK;
 }
 
 gnn_status ensure_device(gnn_ctx* c)
@@ -80,18 +152,8 @@ gnn_status ensure_device(gnn_ctx* c)
     step(upload(D.tw, M.tw));
     step(upload(D.order, M.order));
     step(upload(D.tperm, M.tperm));
-    for (int dir = 0; dir < 2; ++dir) {
-        const HostMeta::Plan& H = dir == 0 ? M.plan_fwd : M.plan_bwd;
-        DevMeta::Plan& P = dir == 0 ? D.fwd : D.bwd;
-        step(upload(P.range_rows, H.range_rows));
-        step(upload(P.seg_row, H.seg_row));
-        step(upload(P.seg_begin, H.seg_begin));
-        step(upload(P.seg_len, H.seg_len));
-        step(upload(P.long_row, H.long_row));
-        step(upload(P.long_first, H.long_first));
-        step(upload(P.long_nseg, H.long_nseg));
-        step(upload(P.rows_sorted, H.rows_sorted));
-    }
+    step(upload_plan(D.fwd, M.plan_fwd));
+    step(upload_plan(D.bwd, M.plan_bwd));
     if (e != hipSuccess) {
         free_device(D);
         (void)hipGetLastError();
@@ -430,6 +492,50 @@ void compute_fwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, char*
     }
 }
 
+// The transposed operator of partition p as the aggregation kernels take it, with every result
+// row added onto its owner's row of a whole-graph array: the full operator (rows = R_p), or, for
+// the output layer with gnn_set_masked_backward, its entries at train vertices only.
+struct TransposedOp {
+    const int64_t* rp;
+    const int32_t* col;
+    const float* w;
+    int64_t nrows;
+    SpmmItems items;
+    SpmmScatter sc;
+};
+static TransposedOp transposed_op(gnn_ctx* c, int32_t layer, int32_t p)
+{
+    const HostMeta& M = c->M;
+    TransposedOp op;
+    if (layer == c->L && c->masked_transpose()) {
+        const HostMeta::MaskedTranspose& T = M.masked_t;
+        const int64_t t0 = T.toff[(size_t)p];
+        op.rp = c->D.masked_t.trp + t0;
+        op.col = c->D.masked_t.tcol;
+        op.w = c->D.masked_t.tw;
+        op.nrows = T.toff[(size_t)p + 1] - t0;
+        op.items = plan_items(T.plan, c->D.masked_t.plan, p);
+        op.items.avg_len = (float)(T.trp[(size_t)(t0 + op.nrows)] - T.trp[(size_t)t0]) / (float)std::max<int64_t>(1, op.nrows);
+        op.sc.n_own = 0;                       // every kept row names its owner
+        op.sc.base_row = 0;
+        op.sc.idx = c->D.masked_t.out_row + t0;
+        return op;
+    }
+    const int64_t r0 = M.off[(size_t)p], np = M.off[(size_t)p + 1] - r0;
+    const int64_t nb = M.boff[(size_t)p + 1] - M.boff[(size_t)p];
+    const int64_t t0 = M.toff[(size_t)p];
+    op.rp = c->D.trp + t0;
+    op.col = c->D.tcol;
+    op.w = c->D.tw;
+    op.nrows = np + nb;
+    op.items = plan_items(M.plan_bwd, c->D.bwd, p);
+    op.items.avg_len = (float)(M.trp[(size_t)M.toff[(size_t)p + 1]] - M.trp[(size_t)t0]) / (float)std::max<int64_t>(1, np + nb);
+    op.sc.n_own = np;
+    op.sc.base_row = r0;
+    op.sc.idx = c->D.bnd + M.boff[(size_t)p];
+    return op;
+}
+
 const char* compute_bwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, const float* g_own,
                         const char* act_own, float* fused_gprev, const SpmmScatter* fused_map, hipStream_t s)
 {
@@ -489,30 +595,26 @@ const char* compute_bwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own
             if (b16) launch_gemm_bf16_nt(dY, dout, W, dout, dZ, 1, din, np, din, dout, ep, s);
             else launch_gemm_nt((const float*)dY, dout, (const float*)W, dout, (float*)dZ, din, np, din, dout, ep, s);
         }
-        const int64_t t0 = M.toff[(size_t)p];
-        SpmmItems items = plan_items(M.plan_bwd, c->D.bwd, p);
-        items.avg_len = (float)(M.trp[(size_t)M.toff[(size_t)p + 1]] - M.trp[(size_t)t0]) / (float)std::max<int64_t>(1, np + nb);
         float* segpart = (float*)(c->scratch + c->ws.segpart);
         // With fused_gprev the transposed aggregation adds each row of the gathered-row gradient
         // straight onto its owner row of grad A^{l-1} (own rows in place, boundary rows through
         // B_p) instead of writing it to scratch for a separate scatter-add pass.
-        SpmmScatter sc;
-        float* out = dGA;
-        if (fused_gprev) {
-            sc.n_own = np;
-            sc.base_row = M.off[(size_t)p];
-            sc.idx = c->D.bnd + M.boff[(size_t)p];
-            if (fused_map) sc = *fused_map;      // another row numbering of the same owners
-            out = fused_gprev;
+        TransposedOp op = transposed_op(c, fused_gprev && !fused_map ? layer : 0, p);
+        float* out = fused_gprev;
+        if (!fused_gprev) {
+            op.sc = SpmmScatter{};
+            out = dGA;
+        } else if (fused_map) {
+            op.sc = *fused_map;                  // another row numbering of the same owners
         }
         {
             Timed t(c, s, GNN_K_SPMM_T);
-            launch_spmm(c->D.trp + t0, c->D.tcol, c->D.tw, nullptr, dZ, np, nullptr, out, np + nb, din,
-                        b16 ? 1 : 0, 0, items, segpart, 0, sc, s);
+            launch_spmm(op.rp, op.col, op.w, nullptr, dZ, np, nullptr, out, op.nrows, din,
+                        b16 ? 1 : 0, 0, op.items, segpart, 0, op.sc, s);
         }
-        if (items.nlong > 0) {
+        if (op.items.nlong > 0) {
             Timed t(c, s, GNN_K_SPMM_REDUCE);
-            launch_spmm_reduce(nullptr, out, din, 0, items, segpart, sc, s);
+            launch_spmm_reduce(nullptr, out, din, 0, op.items, segpart, op.sc, s);
         }
     }
     return dY;
@@ -676,23 +778,17 @@ void xf_aggregate_bwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own_c
                 // (the first thing written to these rows of grad A^{l-1})
                 compute_bwd_self(c, layer, p, (const char*)dYbuf, gprev_own, s, 0);
         }
-        const int64_t t0b = M.toff[(size_t)p];
-        SpmmItems itb = plan_items(M.plan_bwd, c->D.bwd, p);
-        itb.avg_len = (float)(M.trp[(size_t)M.toff[(size_t)p + 1]] - M.trp[(size_t)t0b]) / (float)std::max<int64_t>(1, np + nb);
+        const TransposedOp opb = transposed_op(c, layer, p);
         float* segb = (float*)(c->scratch + c->ws.segpart);
-        SpmmScatter scb;
-        scb.n_own = np;
-        scb.base_row = r0;
-        scb.idx = c->D.bnd + M.boff[(size_t)p];
         float* gHb = (float*)c->ghbuf;
         {
             Timed t(c, s, GNN_K_SPMM_T);
-            launch_spmm(c->D.trp + t0b, c->D.tcol, c->D.tw, nullptr, dYbuf, np, nullptr, gHb, np + nb, dp, 1, 0, itb,
-                        segb, 0, scb, s);
+            launch_spmm(opb.rp, opb.col, opb.w, nullptr, dYbuf, np, nullptr, gHb, opb.nrows, dp, 1, 0, opb.items,
+                        segb, 0, opb.sc, s);
         }
-        if (itb.nlong > 0) {
+        if (opb.items.nlong > 0) {
             Timed t(c, s, GNN_K_SPMM_REDUCE);
-            launch_spmm_reduce(nullptr, gHb, dp, 0, itb, segb, scb, s);
+            launch_spmm_reduce(nullptr, gHb, dp, 0, opb.items, segb, opb.sc, s);
         }
         return;
     }
@@ -737,23 +833,17 @@ void xf_aggregate_bwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own_c
             launch_gemm_nt(dYp, dp, ws.p, ws.ld, gprev_own, din, np, din, dp, ep, s);
         }
     }
-    const int64_t t0 = M.toff[(size_t)p];
-    SpmmItems items = plan_items(M.plan_bwd, c->D.bwd, p);
-    items.avg_len = (float)(M.trp[(size_t)M.toff[(size_t)p + 1]] - M.trp[(size_t)t0]) / (float)std::max<int64_t>(1, np + nb);
+    const TransposedOp op = transposed_op(c, layer, p);
     float* segpart = (float*)(c->scratch + c->ws.segpart);
-    SpmmScatter sc;
-    sc.n_own = np;
-    sc.base_row = r0;
-    sc.idx = c->D.bnd + M.boff[(size_t)p];
     float* gH = (float*)c->ghbuf;
     {
         Timed t(c, s, GNN_K_SPMM_T);
-        launch_spmm(c->D.trp + t0, c->D.tcol, c->D.tw, nullptr, dYp, np, nullptr, gH, np + nb, dp, 0, 0, items,
-                    segpart, 0, sc, s);
+        launch_spmm(op.rp, op.col, op.w, nullptr, dYp, np, nullptr, gH, op.nrows, dp, 0, 0, op.items,
+                    segpart, 0, op.sc, s);
     }
-    if (items.nlong > 0) {
+    if (op.items.nlong > 0) {
         Timed t(c, s, GNN_K_SPMM_REDUCE);
-        launch_spmm_reduce(nullptr, gH, dp, 0, items, segpart, sc, s);
+        launch_spmm_reduce(nullptr, gH, dp, 0, op.items, segpart, op.sc, s);
     }
 }
 
@@ -1071,6 +1161,8 @@ gnn_status gnn_bind(gnn_ctx* c, const void* feat, void* const* act, void* const*
     }
     c->labels = labels;
     c->mask = train_mask;
+    free_masked(c->D.masked_t);           // belongs to the mask bound before
+    if (c->masked_bwd && !c->streaming() && c->model != GNN_GAT && (st = build_masked(c)) != GNN_OK) return st;
     c->staging = (char*)staging;
     c->scratch = (char*)scratch;
     // whole-graph buffers of transform-first layers: in scratch (resident schedule) or given out
@@ -1161,6 +1253,31 @@ gnn_status gnn_set_gather_fusion(gnn_ctx* c, int32_t on)
     c->fuse_gather = on == 1;
     c->staged_layer = c->staged_p = -1;       // staging holds nothing the other mode could use
     if (c->fuse_gather && c->D.ready && !c->streaming() && c->model != GNN_GAT) return ensure_global_columns(c);
+    return GNN_OK;
+}
+
+gnn_status gnn_set_masked_backward(gnn_ctx* c, int32_t on)
+{
+    if (!c) return GNN_EINVAL;
+    if (on != 0 && on != 1) return c->fail(GNN_EINVAL, "gnn_set_masked_backward takes 0 or 1");
+    c->masked_bwd = on == 1;
+    if (!c->masked_bwd) {
+        free_masked(c->D.masked_t);
+        return GNN_OK;
+    }
+    if (c->bound && !c->streaming() && c->model != GNN_GAT && !c->D.masked_t.ready) return build_masked(c);
+    return GNN_OK;
+}
+
+gnn_status gnn_get_masked_backward_size(const gnn_ctx* c, int64_t* entries, int64_t* rows)
+{
+    if (!c || !entries || !rows) return GNN_EINVAL;
+    *entries = *rows = 0;
+    if (c->masked_transpose()) {
+        const HostMeta::MaskedTranspose& T = c->M.masked_t;
+        *rows = T.toff.back();
+        *entries = T.trp.back();
+    }
     return GNN_OK;
 }
 

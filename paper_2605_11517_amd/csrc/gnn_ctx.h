@@ -35,6 +35,15 @@ struct DevMeta {
         int32_t* long_nseg = nullptr;
         int32_t* rows_sorted = nullptr;
     } fwd, bwd;
+    // output layer's transposed operator restricted to train vertices (HostMeta::MaskedTranspose)
+    struct Masked {
+        int64_t* trp = nullptr;
+        int32_t* tcol = nullptr;
+        float* tw = nullptr;
+        int32_t* out_row = nullptr;
+        Plan plan;
+        bool ready = false;
+    } masked_t;
     bool ready = false;
 };
 
@@ -124,6 +133,10 @@ struct gnn_ctx {
     // column indices that name rows of the whole-graph array, and no staging copy is made
     bool fuse_gather = false;
     bool gather_fused() const { return fuse_gather && !streaming() && model != GNN_GAT && D.gcol != nullptr; }
+    // The output layer's transposed aggregation runs over the operator entries of train vertices
+    // only (the gradient of the loss is zero elsewhere); the sub-operator is built by gnn_bind
+    bool masked_bwd = false;
+    bool masked_transpose() const { return masked_bwd && !streaming() && model != GNN_GAT && D.masked_t.ready; }
     bool stream_xf_ok = false;               // set by update_stream_xf() once the partitions exist
     // bytes of the whole-graph buffers the transform-first layers (by the cost rule) would need
     int64_t xf_buffer_bytes(int64_t n) const

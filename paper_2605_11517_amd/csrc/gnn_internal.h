@@ -64,6 +64,17 @@ struct HostMeta {
         std::vector<int64_t> rows_off;    // k+1, offsets into rows_sorted
         std::vector<int32_t> rows_sorted; // short rows (local ids) by entry count, longest first
     } plan_fwd, plan_bwd;
+    // Transposed operator of the output layer restricted to train vertices (see
+    // build_masked_transpose): per partition the rows of R_p that keep at least one entry.
+    struct MaskedTranspose {
+        std::vector<int64_t> toff;      // k+1, offset of partition p's kept rows in trp / out_row
+        std::vector<int64_t> trp;       // kept rows + 1, positions into tcol / tw
+        std::vector<int32_t> tcol;      // local destination row (a train vertex of the partition)
+        std::vector<float> tw;
+        std::vector<int32_t> out_row;   // per kept row: the row of the whole-graph array it adds to
+        Plan plan;
+        bool ready = false;
+    } masked_t;
 };
 
 // Rows with more entries than this are cut into segments of this many entries, each handled
@@ -75,6 +86,13 @@ constexpr int32_t kSpmmRangeRows = 64;
 gnn_status build_host_meta(int model, int64_t n, const int64_t* rowptr, const int32_t* colidx,
                            int32_t k, int32_t mode, uint64_t seed, const int32_t* user_part,
                            bool want_runs, HostMeta& out, std::string& err);
+
+// The gradient of the loss is zero in every row outside the train mask, so the transposed
+// aggregation of the output layer needs only the operator entries whose destination is a train
+// vertex.  Builds that sub-operator of every partition's transpose from M and the mask (rows in
+// library order): kept entries in their original order, rows without a kept entry dropped, the
+// owner row of every kept row, and the work items.  Throws std::bad_alloc.
+void build_masked_transpose(HostMeta& M, const uint8_t* mask);
 
 // ---- kernel launchers (all enqueue on `s`; sizes already validated by the caller) --------
 

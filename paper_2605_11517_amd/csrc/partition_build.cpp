@@ -510,6 +510,66 @@ void append_plan(HostMeta::Plan& G, int32_t k, std::vector<PlanPart>& parts)
 
 }  // namespace
 
+void build_masked_transpose(HostMeta& M, const uint8_t* mask)
+{
+    HostMeta::MaskedTranspose& T = M.masked_t;
+    T = HostMeta::MaskedTranspose{};
+    const int32_t k = (int32_t)M.off.size() - 1;
+    struct Part {
+        std::vector<int64_t> len;       // kept entries of every kept row
+        std::vector<int32_t> tcol, out_row;
+        std::vector<float> tw;
+    };
+    std::vector<Part> parts((size_t)k);
+    parallel_for(k, 1, [&](int, int64_t p) {
+        Part& P = parts[(size_t)p];
+        const int64_t r0 = M.off[(size_t)p], np = M.off[(size_t)p + 1] - r0;
+        const int64_t t0 = M.toff[(size_t)p], nR = M.toff[(size_t)p + 1] - t0;
+        const int64_t b0 = M.boff[(size_t)p];
+        const uint8_t* m = mask + r0;
+        for (int64_t i = 0; i < nR; ++i) {
+            int64_t kept = 0;
+            for (int64_t e = M.trp[(size_t)(t0 + i)]; e < M.trp[(size_t)(t0 + i) + 1]; ++e) {
+                const int32_t v = M.tcol[(size_t)e];
+                if (!m[v]) continue;
+                P.tcol.push_back(v);
+                P.tw.push_back(M.tw[(size_t)e]);
+                ++kept;
+            }
+            if (kept) {
+                P.len.push_back(kept);
+                P.out_row.push_back(i < np ? (int32_t)(r0 + i) : M.bnd[(size_t)(b0 + i - np)]);
+            }
+        }
+    });
+    T.toff.assign((size_t)k + 1, 0);
+    int64_t entries = 0;
+    for (int32_t p = 0; p < k; ++p) {
+        T.toff[(size_t)p + 1] = T.toff[(size_t)p] + (int64_t)parts[(size_t)p].len.size();
+        entries += (int64_t)parts[(size_t)p].tcol.size();
+    }
+    T.trp.reserve((size_t)T.toff[(size_t)k] + 1);
+    T.tcol.reserve((size_t)entries);
+    T.tw.reserve((size_t)entries);
+    T.out_row.reserve((size_t)T.toff[(size_t)k]);
+    T.trp.push_back(0);
+    for (int32_t p = 0; p < k; ++p) {
+        Part& P = parts[(size_t)p];
+        for (int64_t len : P.len) T.trp.push_back(T.trp.back() + len);
+        T.tcol.insert(T.tcol.end(), P.tcol.begin(), P.tcol.end());
+        T.tw.insert(T.tw.end(), P.tw.begin(), P.tw.end());
+        T.out_row.insert(T.out_row.end(), P.out_row.begin(), P.out_row.end());
+        P = Part{};
+    }
+    std::vector<PlanPart> plan((size_t)k);
+    parallel_for(k, 1, [&](int, int64_t p) {
+        const int64_t t0 = T.toff[(size_t)p];
+        plan_partition(T.trp.data() + t0, T.toff[(size_t)p + 1] - t0, plan[(size_t)p]);
+    });
+    append_plan(T.plan, k, plan);
+    T.ready = true;
+}
+
 gnn_status build_host_meta(int model, int64_t n, const int64_t* rowptr, const int32_t* colidx,
                            int32_t k, int32_t mode, uint64_t seed, const int32_t* user_part,
                            bool want_runs, HostMeta& M, std::string& err)

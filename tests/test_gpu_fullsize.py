@@ -55,7 +55,7 @@ def test_mid_workload_full_size(capsys):
 
     # the configuration bench.py times: switching-aware partitions, layer order by rows moved
     s = Session("sage", dims, rowptr, colidx, cfg["k"], cfg["part"], cfg["seed"], X, w, y, m,
-                layer_order="auto", fuse_gather=True)           # the configuration bench.py times
+                layer_order="auto", fuse_gather=True, masked_backward=True)   # the configuration bench.py times
     assert s.ctx.gather_is_fused()
     assert [s.ctx.layer_is_transform_first(l) for l in (1, 2, 3)] == [False, True, True]
     loss = s.epoch()
@@ -185,7 +185,7 @@ def test_dense_workload_sampled(capsys):
         layer["W"] = to_bf16_grid(layer["W"])
     say("inputs ready: n=%d entries=%d" % (n, rowptr[-1]))
     s = Session("gcn", dims, rowptr, colidx, cfg["k"], cfg["part"], cfg["seed"], X, w, y, m,
-                dtype="bf16", layer_order="auto", fuse_gather=True)   # the configuration bench.py times
+                dtype="bf16", layer_order="auto", fuse_gather=True, masked_backward=True)   # as bench.py times it
     assert s.ctx.gather_is_fused()
     assert [s.ctx.layer_is_transform_first(l) for l in (1, 2, 3)] == [False, True, True]
     loss = s.epoch()
@@ -453,7 +453,7 @@ def test_large_workload_sampled(capsys):
     say("inputs ready")
     # the configuration bench.py times: device-counted switching-aware partitions, layer order by rows moved
     s = Session("gcn", dims, rowptr, colidx, cfg["k"], cfg["part"], cfg["seed"], X, w, y, m,
-                layer_order="auto", fuse_gather=True, progress=say)   # the configuration bench.py times
+                layer_order="auto", fuse_gather=True, masked_backward=True, progress=say)   # as bench.py times it
     assert s.ctx.gather_is_fused()
     assert cfg["part"] == "switching_device"
     assert [s.ctx.layer_is_transform_first(l) for l in (1, 2, 3)] == [False, True, True]

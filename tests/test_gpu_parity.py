@@ -187,6 +187,77 @@ def test_gather_fused_into_the_aggregation_gives_the_staged_bits(case):
     assert not bool((s.staging == 0xFF).all()) or k == 1
 
 
+MASKED_BWD = [
+    # (model, dims, n, m_draw, symmetric, k, mode, dtype, layer order, train fraction)
+    ("gcn", (64, 64, 16), 10000, 100000, True, 4, "random", "f32", "aggregate", 0.1),
+    ("gcn", (128, 128, 128, 172), 4000, 50000, False, 7, "lp", "f32", "auto", 0.1),     # the headline's shape
+    ("sage", (100, 256, 256, 47), 3000, 40000, True, 5, "lp", "f32", "auto", 0.1),
+    ("sage", (100, 256, 256, 47), 3000, 40000, True, 5, "lp", "f32", "aggregate", 0.3),
+    ("gcn", (36, 40, 8), 2500, 90000, True, 3, "lp", "f32", "aggregate", 0.5),          # hubs: segments
+    ("gcn", (36, 40, 8), 2500, 90000, True, 3, "lp", "f32", "auto", 0.02),
+    ("gcn", (7, 9, 5), 300, 1500, True, 3, "random", "f32", "aggregate", 0.2),           # scalar loads
+    ("gcn", (64, 128, 64, 16), 3000, 30000, True, 4, "lp", "bf16", "auto", 0.1),
+    ("sage", (72, 136, 8), 2000, 16000, True, 3, "random", "bf16", "aggregate", 0.1),
+    ("gcn", (64, 32, 8), 500, 4000, True, 2, "random", "f32", "aggregate", 0.0),         # nobody trains
+    ("sage", (24, 32, 6), 500, 4000, True, 2, "random", "f32", "auto", 1.0),             # everybody does
+]
+
+
+@pytest.mark.parametrize("case", MASKED_BWD,
+                         ids=lambda c: "%s-%s-k%d-%s-%s-%g" % (c[0], "x".join(map(str, c[1])), c[5], c[7], c[8], c[9]))
+def test_output_layer_backward_over_train_vertices_only(case):
+    """gnn_set_masked_backward(1): the output layer's transposed aggregation runs over the operator
+    entries of train vertices only.  The entries left out multiply gradient rows that are exactly
+    zero: forward results are the same bits, gradients agree with the full operator up to the order
+    of the additions, and (fp32) everything is within the gate of the oracle."""
+    model, dims, n, m_draw, sym, k, mode, dtype, order, frac = case
+    say("case masked backward %s" % (case,))
+    from paper_2605_11517_amd import Session
+    from synth import to_bf16_grid
+    rowptr, colidx = small_graph(n, m_draw, seed=71, symmetric=sym, self_loops=(model == "gcn"))
+    cfg = dict(model=model, dims=dims, seed=23, train_frac=0.5)
+    X, y, m, w = make_inputs(cfg, n)
+    rng = np.random.default_rng(5)
+    m = (rng.random(n) < frac).astype(np.uint8) if 0.0 < frac < 1.0 else np.full(n, int(frac), dtype=np.uint8)
+    if dtype == "bf16":
+        X = to_bf16_grid(X)
+        for layer in w:
+            layer["W"] = to_bf16_grid(layer["W"])
+            if layer["Ws"] is not None:
+                layer["Ws"] = to_bf16_grid(layer["Ws"])
+    s = Session(model, dims, rowptr, colidx, k, mode, 3, X, w, y, m, dtype=dtype, layer_order=order)
+    loss0 = s.epoch()
+    full = s.results()
+    s.set_masked_backward(True)
+    for a in s.gact:
+        a.fill_(float("nan"))                   # every row the backward pass owes must be written
+    loss1 = s.epoch()
+    assert loss1 == loss0 or (np.isnan(loss0) and np.isnan(loss1))
+    got = s.results()
+    for l, (a, b) in enumerate(zip(got["act"], full["act"])):
+        assert np.array_equal(a.view(np.uint32), b.view(np.uint32)), ("act", l)
+    for key in ("gact", "gW", "gWs", "gb"):
+        for l, (a, b) in enumerate(zip(got[key], full[key])):
+            if a is None:
+                continue
+            assert np.isfinite(a).all(), (key, l)
+            assert rel_err(a, b) <= 2e-6, (key, l, rel_err(a, b))
+    if dtype == "f32" and frac > 0.0:
+        fwd = og.forward(model, rowptr, colidx, dims, X, w)
+        ref = aligned_backward(og, fwd, got["act"], w, X, y, m, TOL)
+        assert abs(loss1 - ref["loss"]) <= TOL * abs(ref["loss"])
+        compare(got, ref, model, tag="masked backward")
+    # a second session that binds with the switch on from the start gives the same bits
+    s2 = Session(model, dims, rowptr, colidx, k, mode, 3, X, w, y, m, dtype=dtype, layer_order=order,
+                 masked_backward=True, fuse_gather=True)
+    assert s2.epoch() == loss1 or np.isnan(loss1)
+    again = s2.results()
+    for key in ("act", "gact", "gW", "gWs", "gb"):
+        for l, (a, b) in enumerate(zip(again[key], got[key])):
+            if a is not None:
+                assert np.array_equal(a.view(np.uint32), b.view(np.uint32)), (key, l)
+
+
 def test_two_epochs_are_bit_identical_and_stepping_by_hand_equals_epoch():
     say("case determinism + hand stepping")
     import torch
