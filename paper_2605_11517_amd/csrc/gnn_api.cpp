@@ -570,7 +570,9 @@ const char* compute_bwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own
             launch_act_bwd(g_own, (const float*)act_own, (float*)dYbuf, np, dout, gb, colpart, drop_scale, s);
             dY = dYbuf;
         } else {
-            launch_act_bwd(g_own, nullptr, nullptr, np, dout, gb, colpart, 1.f, s);
+            // output layer: grad A^L is the loss kernel's, zero outside the train mask
+            launch_act_bwd(g_own, nullptr, nullptr, np, dout, gb, colpart, 1.f, s,
+                           c->streaming() ? nullptr : c->mask + M.off[(size_t)p]);
         }
     }
     // recompute the aggregate from the regathered rows
@@ -804,7 +806,9 @@ void xf_aggregate_bwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own_c
                            colpart, drop_scale, s);
             dY = dYbuf;
         } else {
-            launch_act_bwd(g_own, nullptr, nullptr, np, dout, gb, colpart, 1.f, s);
+            // output layer: grad A^L is the loss kernel's, zero outside the train mask
+            launch_act_bwd(g_own, nullptr, nullptr, np, dout, gb, colpart, 1.f, s,
+                           c->streaming() ? nullptr : c->mask + r0);
         }
     }
     const float* in_own = (const float*)in_own_c;

@@ -228,8 +228,10 @@ void launch_act_bwd_bf16(const float* g, const void* act, void* dy, int64_t rows
 // scale = 1 / (1 - p) when dropout followed the activation (the dropped elements are the
 // zeros of act), else 1.
 // `partial` holds ceil(rows / 64) * d floats.
+// row_on (act == null only; may be null): rows with row_on[r] == 0 are known to be zero in g and
+// are not read.
 void launch_act_bwd(const float* g, const float* act, float* dy, int64_t rows, int32_t d,
-                    float* gb, float* partial, float scale, hipStream_t s);
+                    float* gb, float* partial, float scale, hipStream_t s, const uint8_t* row_on = nullptr);
 int64_t act_bwd_partial_floats(int64_t rows, int32_t d);
 
 // softmax cross-entropy over masked rows; grad[n, c]; *loss_dev = mean loss.  count_dev

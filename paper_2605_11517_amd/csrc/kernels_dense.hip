@@ -38,26 +38,39 @@ __global__ __launch_bounds__(kBlock) void k_loss(const float* __restrict__ logit
     const float inv_count = cnt ? 1.f / (float)cnt : 0.f;
     const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
     float term = 0.f;
+    // the wavefront's rows: their mask bytes in one read, then the zero rows (nothing to wait for,
+    // the stores follow each other), then the train rows one by one
+    const int64_t v0 = ((int64_t)blockIdx.x * (kBlock / kWave) + wave) * kLossRowsPerWave;
+    const bool mine = lane < kLossRowsPerWave && v0 + lane < n;
+    const unsigned long long in_range = __ballot(mine);
+    const unsigned long long train = __ballot(mine && mask[v0 + lane] != 0);
+    const bool vec = (c & 3) == 0 && (reinterpret_cast<uintptr_t>(grad) & 15) == 0;
     for (int it = 0; it < kLossRowsPerWave; ++it) {
-        const int64_t v = ((int64_t)blockIdx.x * (kBlock / kWave) + wave) * kLossRowsPerWave + it;
-        if (v >= n) break;
-        const float* x = logits + v * c;
-        float* g = grad + v * c;
-        if (mask[v]) {
-            float mx = -INFINITY;
-            for (int j = lane; j < c; j += kWave) mx = fmaxf(mx, x[j]);
-            mx = wave_max(mx);
-            float se = 0.f;
-            for (int j = lane; j < c; j += kWave) se += expf(x[j] - mx);
-            se = wave_sum(se);
-            const float lse = mx + logf(se);
-            const int32_t y = labels[v];
-            term += lse - x[y];
-            for (int j = lane; j < c; j += kWave)
-                g[j] = (expf(x[j] - lse) - (j == y ? 1.f : 0.f)) * inv_count;
+        if (!((in_range >> it) & 1ull) || ((train >> it) & 1ull)) continue;
+        float* g = grad + (v0 + it) * c;
+        if (vec) {
+            for (int j = lane; j < (c >> 2); j += kWave)
+                reinterpret_cast<float4*>(g)[j] = make_float4(0.f, 0.f, 0.f, 0.f);
         } else {
             for (int j = lane; j < c; j += kWave) g[j] = 0.f;
         }
+    }
+    for (int it = 0; it < kLossRowsPerWave; ++it) {
+        if (!((train >> it) & 1ull)) continue;
+        const int64_t v = v0 + it;
+        const float* x = logits + v * c;
+        float* g = grad + v * c;
+        float mx = -INFINITY;
+        for (int j = lane; j < c; j += kWave) mx = fmaxf(mx, x[j]);
+        mx = wave_max(mx);
+        float se = 0.f;
+        for (int j = lane; j < c; j += kWave) se += expf(x[j] - mx);
+        se = wave_sum(se);
+        const float lse = mx + logf(se);
+        const int32_t y = labels[v];
+        term += lse - x[y];
+        for (int j = lane; j < c; j += kWave)
+            g[j] = (expf(x[j] - lse) - (j == y ? 1.f : 0.f)) * inv_count;
     }
     if (lane == 0) wsum[wave] = term;
     __syncthreads();
@@ -114,7 +127,7 @@ __global__ __launch_bounds__(kBlock) void k_act_bwd(const float* __restrict__ g,
                                                     const float* __restrict__ act,
                                                     float* __restrict__ dy, int64_t rows,
                                                     int32_t d, float* __restrict__ partial,
-                                                    float scale)
+                                                    float scale, const uint8_t* __restrict__ row_on)
 {
     __shared__ float sm[kBlock];
     const int64_t r0 = (int64_t)blockIdx.x * kRowsPerBlockAct;
@@ -132,7 +145,7 @@ __global__ __launch_bounds__(kBlock) void k_act_bwd(const float* __restrict__ g,
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const int64_t rr = r + (int64_t)u * rpp;
-                    const bool ok = rr < r1;
+                    const bool ok = rr < r1 && (!row_on || row_on[rr]);   // other rows of g are zero
                     gv[u] = ok ? g[rr * d + c] : 0.f;
                     av[u] = (ok && act) ? act[rr * d + c] : 0.f;
                 }
@@ -166,7 +179,7 @@ __global__ __launch_bounds__(kBlock) void k_act_bwd_vec(const float* __restrict_
                                                         const float* __restrict__ act,
                                                         float* __restrict__ dy, int64_t rows,
                                                         int32_t d, float* __restrict__ partial,
-                                                        float scale)
+                                                        float scale, const uint8_t* __restrict__ row_on)
 {
     __shared__ float4 sm[kBlock];
     const int cw = d / 4;
@@ -186,7 +199,7 @@ __global__ __launch_bounds__(kBlock) void k_act_bwd_vec(const float* __restrict_
                     const int64_t rr = r + (int64_t)u * rpp;
                     gv[u] = make_float4(0.f, 0.f, 0.f, 0.f);
                     av[u] = make_float4(1.f, 1.f, 1.f, 1.f);
-                    if (rr < r1) {
+                    if (rr < r1 && (!row_on || row_on[rr])) {              // other rows of g are zero
                         gv[u] = reinterpret_cast<const float4*>(g + rr * d)[cidx];
                         if (act) av[u] = reinterpret_cast<const float4*>(act + rr * d)[cidx];
                     }
@@ -518,9 +531,10 @@ int64_t act_bwd_partial_floats(int64_t rows, int32_t d)
 }
 
 void launch_act_bwd(const float* g, const float* act, float* dy, int64_t rows, int32_t d,
-                    float* gb, float* partial, float scale, hipStream_t s)
+                    float* gb, float* partial, float scale, hipStream_t s, const uint8_t* row_on)
 {
     if (!act) scale = 1.f;
+    if (act) row_on = nullptr;                  // dy is written for every row
     if (rows <= 0) return;
     const int64_t blocks = (rows + kRowsPerBlockAct - 1) / kRowsPerBlockAct;
     if (!act && !gb) return;
@@ -529,10 +543,10 @@ void launch_act_bwd(const float* g, const float* act, float* dy, int64_t rows, i
                                      reinterpret_cast<uintptr_t>(partial)) & 15) == 0;
     if (vec)
         hipLaunchKernelGGL(k_act_bwd_vec, dim3((unsigned)blocks), dim3(kBlock), 0, s, g, act, dy, rows,
-                           d, partial, scale);
+                           d, partial, scale, row_on);
     else
         hipLaunchKernelGGL(k_act_bwd, dim3((unsigned)blocks), dim3(kBlock), 0, s, g, act, dy, rows, d,
-                           partial, scale);
+                           partial, scale, row_on);
     if (gb)
         hipLaunchKernelGGL(k_colsum_finish, dim3((unsigned)((d + 31) / 32)), dim3(32 * kFinishGroups),
                            0, s, (const float*)partial, blocks, d, gb);

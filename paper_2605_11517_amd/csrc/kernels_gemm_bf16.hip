@@ -409,59 +409,12 @@ __device__ inline void wide_issue(const bf16_t* __restrict__ p, int64_t ld, int6
     }
 }
 
-// requires: one K segment, K a multiple of 64, 16-byte aligned rows of A and B
-__global__ __launch_bounds__(WTHREADS) void k_gemm_bf16_wide(const Args g)
+// Stores the 256 x 256 tile held in the accumulators of the eight wavefronts: + bias, max(., 0),
+// then bf16 rows through LDS (16 contiguous bytes per lane) or fp32 values straight from the
+// MFMA layout.
+__device__ inline void wide_store(const Args& g, floatx16 (&acc)[4][2], char* wlds, int64_t m0, int32_t n0,
+                                  int wave, int lane, int wm, int wn)
 {
-    extern __shared__ __attribute__((aligned(1024))) char wlds[];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wm = wave >> 2, wn = wave & 3;
-    int64_t mtile;
-    int32_t ntile;
-    if (!tile_of_block(blockIdx.x, (g.m + WBM - 1) / WBM, g.nt_1d, mtile, ntile)) return;
-    const int64_t m0 = mtile * WBM;
-    const int32_t n0 = ntile * WBN;
-    const int nstages = g.kseg[0] / WBK;
-
-    floatx16 acc[4][2];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-    wide_issue(g.a[0], g.lda[0], m0, g.m, 0, wlds, wave, lane);
-    wide_issue(g.b[0], g.ldb[0], n0, g.n, 0, wlds + WBM * WROWB, wave, lane);
-    for (int t = 0; t < nstages; ++t) {
-        const int buf = t & 1;
-        __builtin_amdgcn_s_waitcnt(0x0F70);           // vmcnt(0): this thread's loads of stage t landed
-        __syncthreads();                               // everybody's did; stage t - 1 is no longer read
-        if (t + 1 < nstages) {
-            char* nxt = wlds + (buf ^ 1) * WSTAGE;
-            wide_issue(g.a[0], g.lda[0], m0, g.m, (int64_t)(t + 1) * WBK, nxt, wave, lane);
-            wide_issue(g.b[0], g.ldb[0], n0, g.n, (int64_t)(t + 1) * WBK, nxt + WBM * WROWB, wave, lane);
-        }
-        const char* As = wlds + buf * WSTAGE;
-        const char* Bs = As + WBM * WROWB;
-        const int xl = lane & 31, half = lane >> 5;
-#pragma unroll
-        for (int ks = 0; ks < WBK / 16; ++ks) {
-            bf16x8 av[4], bv[2];
-            const int c = 2 * ks + half;
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                av[i] = *reinterpret_cast<const bf16x8*>(As + wide_chunk(wm * WTM + 32 * i + xl, c));
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-                bv[j] = *reinterpret_cast<const bf16x8*>(Bs + wide_chunk(wn * WTN + 32 * j + xl, c));
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bv[j], acc[i][j], 0, 0, 0);
-        }
-    }
-
     if (g.out_bf16) {
         __syncthreads();                               // every wave is done reading the last stage
         char* patch = wlds + (size_t)wave * WTM * WCS; // private to the wave: [128 rows][64 cols]
@@ -518,6 +471,224 @@ __global__ __launch_bounds__(WTHREADS) void k_gemm_bf16_wide(const Args g)
         }
 }
 
+// requires: one K segment, K a multiple of 64, 16-byte aligned rows of A and B
+__global__ __launch_bounds__(WTHREADS) void k_gemm_bf16_wide(const Args g)
+{
+    extern __shared__ __attribute__((aligned(1024))) char wlds[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave >> 2, wn = wave & 3;
+    int64_t mtile;
+    int32_t ntile;
+    if (!tile_of_block(blockIdx.x, (g.m + WBM - 1) / WBM, g.nt_1d, mtile, ntile)) return;
+    const int64_t m0 = mtile * WBM;
+    const int32_t n0 = ntile * WBN;
+    const int nstages = g.kseg[0] / WBK;
+
+    floatx16 acc[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    wide_issue(g.a[0], g.lda[0], m0, g.m, 0, wlds, wave, lane);
+    wide_issue(g.b[0], g.ldb[0], n0, g.n, 0, wlds + WBM * WROWB, wave, lane);
+    for (int t = 0; t < nstages; ++t) {
+        const int buf = t & 1;
+        __builtin_amdgcn_s_waitcnt(0x0F70);           // vmcnt(0): this thread's loads of stage t landed
+        __syncthreads();                               // everybody's did; stage t - 1 is no longer read
+        if (t + 1 < nstages) {
+            char* nxt = wlds + (buf ^ 1) * WSTAGE;
+            wide_issue(g.a[0], g.lda[0], m0, g.m, (int64_t)(t + 1) * WBK, nxt, wave, lane);
+            wide_issue(g.b[0], g.ldb[0], n0, g.n, (int64_t)(t + 1) * WBK, nxt + WBM * WROWB, wave, lane);
+        }
+        const char* As = wlds + buf * WSTAGE;
+        const char* Bs = As + WBM * WROWB;
+        const int xl = lane & 31, half = lane >> 5;
+#pragma unroll
+        for (int ks = 0; ks < WBK / 16; ++ks) {
+            bf16x8 av[4], bv[2];
+            const int c = 2 * ks + half;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                av[i] = *reinterpret_cast<const bf16x8*>(As + wide_chunk(wm * WTM + 32 * i + xl, c));
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                bv[j] = *reinterpret_cast<const bf16x8*>(Bs + wide_chunk(wn * WTN + 32 * j + xl, c));
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bv[j], acc[i][j], 0, 0, 0);
+        }
+    }
+
+    wide_store(g, acc, wlds, m0, n0, wave, lane, wm, wn);
+}
+
+// ---------------------------------------------------------------------------------------------
+// The same product with a ring of four 32-deep stages instead of two 64-deep ones, and with
+// the fragment reads one step ahead of the MFMAs that use them.
+//
+// What held the two-stage kernel at a third of the matrix pipe: its loop asked for a step's
+// fragments and waited for all of them before the step's MFMAs (the LDS latency was exposed after
+// every four MFMAs), and a stage's loads were in flight for one stage of arithmetic only, less
+// than the latency of a row tile's first fetch from HBM.  Here a stage (256 + 256 rows of 64
+// bytes, 32 KB) is loaded three stages before it is needed... two stages of arithmetic ahead of
+// its first use, three buffers ahead in the ring; a step's fragments (k = 16 of one stage) are
+// requested while the previous step's MFMAs run, across the stage boundary too: the barrier
+// that opens stage t + 1 sits in the middle of stage t.
+//
+// Tile rows are 64 bytes (four 16-byte chunks); chunk c of row x lies in slot c ^ ((x >> 2) & 3),
+// which spreads the sixteen rows of a quarter-wavefront read over all banks.
+constexpr int RBK = 32, RSTAGES = 4;
+constexpr int RROWB = RBK * 2;                         // bytes per tile row
+constexpr int RSTAGE = (WBM + WBN) * RROWB;            // bytes per stage (32 KB)
+constexpr int RLDS = RSTAGES * RSTAGE > 8 * WTM * WCS ? RSTAGES * RSTAGE : 8 * WTM * WCS;
+
+__device__ inline int ring_chunk(int x, int c) { return x * RROWB + ((c ^ ((x >> 2) & 3)) << 4); }
+
+// one operand tile of a stage: 256 rows x 64 bytes, two 1 KB blocks (16 rows each) per wavefront
+__device__ inline void ring_issue(const bf16_t* __restrict__ p, int64_t ld, int64_t row0, int64_t nrows,
+                                  int64_t k0, char* lds_tile, int wave, int lane)
+{
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int q = j * 8 + wave;
+        const int row = q * 16 + (lane >> 2);
+        const int c = (lane & 3) ^ ((row >> 2) & 3);   // LDS slot lane & 3 of the row holds chunk c
+        int64_t gr = row0 + row;
+        gr = gr < nrows ? gr : nrows - 1;              // rows past the end: valid address, result unused
+        const bf16_t* src = p + gr * ld + k0 + c * 8;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                         (__attribute__((address_space(3))) void*)(lds_tile + q * 1024), 16, 0, 0);
+    }
+}
+
+struct RingFrag {
+    bf16x8 a[4], b[2];
+};
+typedef int v4i32 __attribute__((ext_vector_type(4)));
+// The six fragment reads of one step as one asm statement.  The compiler does not see that
+// their results arrive later, so it places no wait of its own; the kernel waits by count at the
+// points marked below.  (Written as plain loads, the reads of the next step would be waited for
+// together with those of the current one: the compiler's wait before a step's first MFMA covers
+// everything outstanding whenever some path into the block has nothing newer in flight.)
+// a_addr / b_addr: LDS byte address of this lane's chunk in row block 0 of the A / B tile; the
+// other row blocks are 32 rows (2048 bytes) further each.
+__device__ inline void ring_frags(RingFrag& f, uint32_t a_addr, uint32_t b_addr)
+{
+    v4i32 a0, a1, a2, a3, b0, b1;
+    asm volatile(
+        "ds_read_b128 %0, %6\n\t"
+        "ds_read_b128 %1, %6 offset:2048\n\t"
+        "ds_read_b128 %2, %6 offset:4096\n\t"
+        "ds_read_b128 %3, %6 offset:6144\n\t"
+        "ds_read_b128 %4, %7\n\t"
+        "ds_read_b128 %5, %7 offset:2048"
+        : "=&v"(a0), "=&v"(a1), "=&v"(a2), "=&v"(a3), "=&v"(b0), "=&v"(b1)
+        : "v"(a_addr), "v"(b_addr)
+        : "memory");
+    f.a[0] = __builtin_bit_cast(bf16x8, a0);
+    f.a[1] = __builtin_bit_cast(bf16x8, a1);
+    f.a[2] = __builtin_bit_cast(bf16x8, a2);
+    f.a[3] = __builtin_bit_cast(bf16x8, a3);
+    f.b[0] = __builtin_bit_cast(bf16x8, b0);
+    f.b[1] = __builtin_bit_cast(bf16x8, b1);
+}
+__device__ inline void ring_mfma(floatx16 (&acc)[4][2], const RingFrag& f)
+{
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
+}
+// waits until at most `pending` of this wavefront's LDS reads are outstanding (6: the step just
+// requested; 0: none), and keeps the compiler from moving anything across
+#define RING_WAIT_LDS(pending)                                             \
+    do {                                                                   \
+        __builtin_amdgcn_sched_barrier(0);                                 \
+        __builtin_amdgcn_s_waitcnt(0xC07F | ((pending) << 8));             \
+        __builtin_amdgcn_sched_barrier(0);                                 \
+    } while (0)
+
+// requires: one K segment, K a multiple of 32, 16-byte aligned rows of A and B
+__global__ __launch_bounds__(WTHREADS) void k_gemm_bf16_ring(const Args g)
+{
+    extern __shared__ __attribute__((aligned(1024))) char wlds[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave >> 2, wn = wave & 3;
+    int64_t mtile;
+    int32_t ntile;
+    if (!tile_of_block(blockIdx.x, (g.m + WBM - 1) / WBM, g.nt_1d, mtile, ntile)) return;
+    const int64_t m0 = mtile * WBM;
+    const int32_t n0 = ntile * WBN;
+    const int nst = g.kseg[0] / RBK;
+
+    floatx16 acc[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    auto issue = [&](int st) {
+        char* buf = wlds + (st % RSTAGES) * RSTAGE;
+        ring_issue(g.a[0], g.lda[0], m0, g.m, (int64_t)st * RBK, buf, wave, lane);
+        ring_issue(g.b[0], g.ldb[0], n0, g.n, (int64_t)st * RBK, buf + WBM * RROWB, wave, lane);
+    };
+    // every wavefront issues four loads per stage; stages complete in the order they were issued
+    const int ahead = nst < RSTAGES - 1 ? nst : RSTAGES - 1;
+    for (int st = 0; st < ahead; ++st) issue(st);
+    if (ahead >= 3) __builtin_amdgcn_s_waitcnt(0x0F78);        // vmcnt(8): stage 0 has landed
+    else if (ahead == 2) __builtin_amdgcn_s_waitcnt(0x0F74);   // vmcnt(4)
+    else __builtin_amdgcn_s_waitcnt(0x0F70);                   // vmcnt(0)
+    __syncthreads();
+    // this lane's fragment addresses inside a stage, for the two 16-deep steps of a stage
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)wlds;
+    const int xl = lane & 31, half = lane >> 5;
+    uint32_t a_off[2], b_off[2];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+        a_off[ks] = lds0 + (uint32_t)ring_chunk(wm * WTM + xl, 2 * ks + half);
+        b_off[ks] = lds0 + (uint32_t)(WBM * RROWB + ring_chunk(wn * WTN + xl, 2 * ks + half));
+    }
+    RingFrag f0, f1;
+    ring_frags(f0, a_off[0], b_off[0]);
+    RING_WAIT_LDS(0);
+    // (the last stage is peeled off: the loop body has no branch around its LDS reads)
+    for (int t = 0; t + 1 < nst; ++t) {
+        const uint32_t cur = (uint32_t)((t % RSTAGES) * RSTAGE);
+        const uint32_t nxt = (uint32_t)(((t + 1) % RSTAGES) * RSTAGE);
+        ring_frags(f1, a_off[1] + cur, b_off[1] + cur);
+        RING_WAIT_LDS(6);             // f0 is there (requested a step ago); f1 stays in flight
+        ring_mfma(acc, f0);
+        RING_WAIT_LDS(0);             // f1 is there
+        // stage t + 1 must have landed; of the stages issued so far only t + 2 may be pending
+        if (t + 2 < nst) __builtin_amdgcn_s_waitcnt(0x0F74);
+        else __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();              // ... for every wavefront; and nobody reads stage t - 1 any more
+        if (t + RSTAGES - 1 < nst) issue(t + RSTAGES - 1);      // into the buffer stage t - 1 was in
+        ring_frags(f0, a_off[0] + nxt, b_off[0] + nxt);
+        __builtin_amdgcn_sched_barrier(0);
+        ring_mfma(acc, f1);
+        RING_WAIT_LDS(0);             // f0 is there before the values cross the loop edge
+    }
+    if (nst > 0) {
+        const uint32_t cur = (uint32_t)(((nst - 1) % RSTAGES) * RSTAGE);
+        ring_frags(f1, a_off[1] + cur, b_off[1] + cur);
+        RING_WAIT_LDS(6);
+        ring_mfma(acc, f0);
+        RING_WAIT_LDS(0);
+        ring_mfma(acc, f1);
+    }
+    __syncthreads();                  // the store below reuses the ring as staging space
+    wide_store(g, acc, wlds, m0, n0, wave, lane, wm, wn);
+}
+
 // Whether the wide kernel can take this product (both operands k-contiguous is the caller's business).
 bool wide_ok(const Args& g)
 {
@@ -536,11 +707,21 @@ bool launch_wide(const Args& g, hipStream_t s)
 {
     static const bool attr_ok = hipFuncSetAttribute((const void*)k_gemm_bf16_wide,
                                                     hipFuncAttributeMaxDynamicSharedMemorySize, WLDS) == hipSuccess;
-    if (!attr_ok) return false;
+    static const bool ring_ok = hipFuncSetAttribute((const void*)k_gemm_bf16_ring,
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, RLDS) == hipSuccess;
+    static const bool ring = [] {
+        const char* e = getenv("GNNMI_GEMM_RING");
+        return e && e[0] == '1';
+    }();
     const int64_t mt = (g.m + WBM - 1) / WBM;
     const int32_t nt = (g.n + WBN - 1) / WBN;
     Args ga = g;
     ga.nt_1d = nt;
+    if (ring && ring_ok) {
+        hipLaunchKernelGGL(k_gemm_bf16_ring, dim3((unsigned)((mt + 7) / 8 * 8 * nt)), dim3(WTHREADS), RLDS, s, ga);
+        return true;
+    }
+    if (!attr_ok) return false;
     hipLaunchKernelGGL(k_gemm_bf16_wide, dim3((unsigned)((mt + 7) / 8 * 8 * nt)), dim3(WTHREADS), WLDS, s, ga);
     return true;
 }
