@@ -411,7 +411,7 @@ def run_workload(name, args, steps, warmup, want_cpu):
             path = os.path.join(ROOT, "profiles", "pmc_%s_epoch.md" % name)
             table = read_traffic(path)
             if table and args.graph_scale == 1.0:
-                rows = [v for kk, v in table.items() if kk.startswith(("k_spmm_items", "k_spmm_slots"))]
+                rows = [v for kk, v in table.items() if kk.startswith(("k_spmm_items", "k_spmm_slots", "k_spmm_short"))]
                 if rows:
                     tot_l = sum(r["launches"] for r in rows)
                     traffic = sum(r["bytes_per_launch"] * r["launches"] for r in rows) / tot_l
