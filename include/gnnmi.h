@@ -424,6 +424,47 @@ typedef struct {
 } gnn_stream_stats;
 gnn_status gnn_get_stream_stats(const gnn_ctx *ctx, gnn_stream_stats *out);
 
+/* ---- storage tier below host memory (streaming schedule) -------------------------------- */
+
+/* The paper keeps activations and gradients on storage and caches them in host memory: whole
+ * layers while they fit, whole layers evicted in least-recently-used order when they do not
+ * (partition-wise cache management section; its third mode, partition-wise eviction for a layer
+ * larger than host memory, is not built).  gnn_storage_open gives a context with a streaming
+ * budget (hbm_budget_bytes > 0) that tier: every per-layer array (the features A^0, A^1..A^L,
+ * grad A^1..grad A^L, rows in library order) gets a file in `dir` (created, and removed again by
+ * gnn_storage_close / gnn_destroy), and the library allocates one pinned host pool of
+ * host_budget_bytes in which it keeps whole arrays.  Before each phase of gnn_epoch (a layer's
+ * forward pass, the loss, a layer's backward pass) the arrays that phase reads or writes are made
+ * resident: read from their file unless the phase overwrites them completely, evicting the least
+ * recently used arrays that the phase does not need (written to their file first when they
+ * changed).  A helper thread reads the next phase's arrays ahead into free room.  The streaming
+ * schedule itself is unchanged (HBM caches the pool's arrays block by block), so results are the
+ * resident schedule's bits.
+ *
+ * Call after gnn_build_partitions and before gnn_bind; gnn_bind then ignores feat, act and
+ * grad_act (pass NULL).  The features go in with gnn_storage_write(ctx, 0, 0, src) and results
+ * come out with gnn_storage_read; both move one whole array between the tier and ordinary host
+ * memory of the caller (kind 0: A^layer, layer 0..L, storage type of the context, logits fp32;
+ * kind 1: grad A^layer, layer 1..L, fp32).  Host file I/O is synchronous on the calling thread
+ * apart from the helper thread's read-ahead.
+ * GNN_ESTATE without partitions or without a streaming budget; GNN_ENOMEM when the pool cannot
+ * hold the four arrays a backward layer touches or cannot be allocated; GNN_EINVAL when a file
+ * cannot be created; GNN_EHIP for a failed read or write (message in gnn_last_error). */
+gnn_status gnn_storage_open(gnn_ctx *ctx, const char *dir, int64_t host_budget_bytes);
+gnn_status gnn_storage_close(gnn_ctx *ctx);
+gnn_status gnn_storage_write(gnn_ctx *ctx, int32_t kind, int32_t layer, const void *src_host);
+gnn_status gnn_storage_read(gnn_ctx *ctx, int32_t kind, int32_t layer, void *dst_host);
+typedef struct {
+    int64_t host_pool_bytes; /* size of the pinned pool */
+    int64_t array_bytes;     /* all arrays together */
+    int64_t loads, hits;     /* arrays read from their file / found in the pool when a phase asked */
+    int64_t prefetched;      /* of the loads: read ahead by the helper thread */
+    int64_t evictions, writebacks;
+    int64_t bytes_read, bytes_written; /* file traffic since gnn_storage_open */
+    int64_t compactions;     /* times the arrays in the pool were moved together to join free room */
+} gnn_storage_stats;
+gnn_status gnn_get_storage_stats(const gnn_ctx *ctx, gnn_storage_stats *out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -54,6 +54,11 @@ def make_optimizer(kind="adam", lr=0.01, beta1=0.9, beta2=0.999, eps=1e-8, weigh
     return Optimizer({"sgd": 0, "adam": 1}[kind], lr, beta1, beta2, eps, weight_decay)
 
 
+class StorageStats(C.Structure):
+    _fields_ = [(n_, C.c_int64) for n_ in ("host_pool_bytes", "array_bytes", "loads", "hits", "prefetched",
+                                           "evictions", "writebacks", "bytes_read", "bytes_written", "compactions")]
+
+
 class StreamStats(C.Structure):
     _fields_ = [(f, C.c_int64) for f in ("act_loads", "act_hits", "grad_loads", "grad_hits",
                                          "grad_writebacks", "h2d_bytes", "d2h_bytes",
@@ -108,6 +113,11 @@ def load_library():
         "gnn_set_profiling": [vp, i32],
         "gnn_get_profile": [vp, P(C.c_double), P(i64)],
         "gnn_get_stream_stats": [vp, P(StreamStats)],
+        "gnn_storage_open": [vp, C.c_char_p, i64],
+        "gnn_storage_close": [vp],
+        "gnn_storage_write": [vp, i32, i32, vp],
+        "gnn_storage_read": [vp, i32, i32, vp],
+        "gnn_get_storage_stats": [vp, P(StorageStats)],
         "gnn_get_partitioner_history": [vp, P(i32), P(C.c_double), i32],
     }
     for name, args in sig.items():
@@ -313,6 +323,23 @@ class Context:
         """False/0 off, True/1 every kernel class, 2 the aggregation kernels only."""
         self._check(self.lib.gnn_set_profiling(self.h, int(enabled)))
 
+    def storage_open(self, directory, host_budget_bytes):
+        self._check(self.lib.gnn_storage_open(self.h, os.fsencode(directory), int(host_budget_bytes)))
+
+    def storage_close(self):
+        self._check(self.lib.gnn_storage_close(self.h))
+
+    def storage_write(self, kind, layer, src_ptr):
+        self._check(self.lib.gnn_storage_write(self.h, int(kind), int(layer), src_ptr))
+
+    def storage_read(self, kind, layer, dst_ptr):
+        self._check(self.lib.gnn_storage_read(self.h, int(kind), int(layer), dst_ptr))
+
+    def get_storage_stats(self):
+        st = StorageStats()
+        self._check(self.lib.gnn_get_storage_stats(self.h, C.byref(st)))
+        return {name: int(getattr(st, name)) for name, _ in StorageStats._fields_}
+
     def get_stream_stats(self):
         st = StreamStats()
         self._check(self.lib.gnn_get_stream_stats(self.h, C.byref(st)))
@@ -333,7 +360,7 @@ class Session:
     def __init__(self, model, dims, rowptr, colidx, k, part_mode, seed, X, weights, labels,
                  train_mask, has_bias=True, user_part=None, device="cuda:0", dtype="f32",
                  hbm_budget_bytes=0, layer_order="aggregate", fuse_gather=False, masked_backward=False,
-                 progress=None):
+                 storage_dir=None, host_budget_bytes=0, progress=None):
         import torch
         self.torch = torch
         if not torch.cuda.is_available():
@@ -363,7 +390,20 @@ class Session:
         # library order (the library's row permutation); torch only allocates and copies
         self.labels = self._to_library(t.from_numpy(np.ascontiguousarray(labels, dtype=np.int32)).to(self.dev))
         self.mask = self._to_library(t.from_numpy(np.ascontiguousarray(train_mask, dtype=np.uint8)).to(self.dev))
-        if self.streaming:
+        # storage_dir: the per-vertex arrays live in files there and the library caches whole
+        # arrays in a pinned pool of host_budget_bytes (streaming schedule only)
+        self.tiered = storage_dir is not None
+        if self.tiered:
+            if not self.streaming:
+                raise ValueError("storage_dir needs a streaming budget (hbm_budget_bytes)")
+            self.ctx.storage_open(storage_dir, host_budget_bytes)
+            src = self._store(t.from_numpy(np.ascontiguousarray(X, dtype=np.float32)).pin_memory())
+            feat = self._to_library(src)
+            self.ctx.storage_write(0, 0, feat.data_ptr())
+            del src, feat
+            self.feat = None
+            big = None
+        elif self.streaming:
             # pinned (device-mapped) host arrays on both sides: the library's kernels read and
             # write them over the host link
             big = dict(device="cpu", pin_memory=True)
@@ -376,7 +416,7 @@ class Session:
                 self._store(t.from_numpy(np.ascontiguousarray(X, dtype=np.float32)).to(self.dev)))
         say("features placed")
         self.act, self.gact = [], []
-        for l in range(self.L):
+        for l in range(self.L if not self.tiered else 0):
             self.act.append(t.zeros((self.n, dims[l + 1]), dtype=store if l < self.L - 1 else t.float32,
                                     **big))                                  # logits stay fp32
             self.gact.append(t.zeros((self.n, dims[l + 1]), dtype=t.float32, **big))
@@ -472,11 +512,24 @@ class Session:
     def epoch(self):
         return self.ctx.epoch(self.stream)
 
+    def _from_storage(self, kind, layer):
+        """One array of the storage tier as a pinned host tensor in library order."""
+        t = self.torch
+        d = self.dims[layer]
+        dtype = t.float32 if kind == 1 or layer == self.L or not self.bf16 else t.bfloat16
+        buf = t.empty((self.n, d), dtype=dtype, device="cpu", pin_memory=True)
+        self.ctx.storage_read(kind, layer, buf.data_ptr())
+        return buf
+
     def results(self):
         """Everything the oracle also returns, in original vertex order."""
-        out = {"act": [self.to_original(a) for a in self.act],
-               "gact": [self.to_original(g) for g in self.gact],
-               "gW": [], "gWs": [], "gb": []}
+        if self.tiered:
+            acts = [self.to_original(self._from_storage(0, l)) for l in range(1, self.L + 1)]
+            gacts = [self.to_original(self._from_storage(1, l)) for l in range(1, self.L + 1)]
+        else:
+            acts = [self.to_original(a) for a in self.act]
+            gacts = [self.to_original(g) for g in self.gact]
+        out = {"act": acts, "gact": gacts, "gW": [], "gWs": [], "gb": []}
         for l in range(self.L):
             gW, gWs, gb = self.gw[3 * l:3 * l + 3]
             out["gW"].append(gW.cpu().numpy())

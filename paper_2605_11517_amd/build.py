@@ -10,7 +10,7 @@ CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 OBJDIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libgnnmi.so")
-SOURCES = ["gnn_api.cpp", "streaming.cpp", "gat.cpp", "partition_build.cpp", "kernels_sparse.hip", "kernels_partition.hip", "kernels_gat.hip", "kernels_gemm.hip", "kernels_gemm_bf16.hip",
+SOURCES = ["gnn_api.cpp", "streaming.cpp", "storage_tier.cpp", "gat.cpp", "partition_build.cpp", "kernels_sparse.hip", "kernels_partition.hip", "kernels_gat.hip", "kernels_gemm.hip", "kernels_gemm_bf16.hip",
            "kernels_dense.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed fp32 instructions are switched off for all device code

@@ -1013,6 +1013,7 @@ void gnn_destroy(gnn_ctx* c)
 {
     if (!c) return;
     stream_engine_destroy(c);
+    tier_close(c);
     if (c->D.ready) free_device(c->D);
     for (hipEvent_t e : c->events) (void)hipEventDestroy(e);
     for (hipEvent_t e : c->side_events) (void)hipEventDestroy(e);
@@ -1035,6 +1036,7 @@ gnn_status gnn_build_partitions(gnn_ctx* c, int64_t n, const int64_t* rowptr, co
         st = build_host_meta(c->model, n, rowptr, colidx, k, mode, seed, user_part, c->streaming(), M, err);
         if (st != GNN_OK) return c->fail(st, err);
         stream_engine_destroy(c);
+        tier_close(c);                 // its arrays were sized for the graph before
         if (c->D.ready) free_device(c->D);
         c->M = std::move(M);
     } catch (const std::bad_alloc&) {
@@ -1124,12 +1126,14 @@ gnn_status gnn_bind(gnn_ctx* c, const void* feat, void* const* act, void* const*
 {
     if (!c) return GNN_EINVAL;
     if (!c->built) return c->fail(GNN_ESTATE, "gnn_bind before gnn_build_partitions");
-    if (!feat || !act || !grad_act || !weights || !grad_w || !labels || !train_mask || !staging ||
+    // with a storage tier the per-vertex arrays are the tier's: feat, act and grad_act are ignored
+    const bool tiered = c->tier != nullptr;
+    if ((!tiered && (!feat || !act || !grad_act)) || !weights || !grad_w || !labels || !train_mask || !staging ||
         !scratch)
         return c->fail(GNN_EINVAL, "null buffer passed to gnn_bind");
     const int32_t L = c->L;
     for (int32_t l = 0; l < L; ++l) {
-        if (!act[l] || !grad_act[l]) return c->fail(GNN_EINVAL, "null activation or gradient buffer");
+        if (!tiered && (!act[l] || !grad_act[l])) return c->fail(GNN_EINVAL, "null activation or gradient buffer");
         if (!weights[3 * l] || !grad_w[3 * l]) return c->fail(GNN_EINVAL, "null weight or weight-gradient buffer");
         if ((c->model == GNN_SAGE_MEAN || c->model == GNN_GAT) && (!weights[3 * l + 1] || !grad_w[3 * l + 1]))
             return c->fail(GNN_EINVAL, "null self-weight (SAGE) or attention-vector (GAT) buffer");
@@ -1138,9 +1142,9 @@ gnn_status gnn_bind(gnn_ctx* c, const void* feat, void* const* act, void* const*
     }
     // every per-vertex array and every weight matrix is read and written in 16-byte vectors
     uintptr_t bits = reinterpret_cast<uintptr_t>(staging) | reinterpret_cast<uintptr_t>(scratch) |
-                     reinterpret_cast<uintptr_t>(feat);
+                     (tiered ? 0 : reinterpret_cast<uintptr_t>(feat));
     for (int32_t l = 0; l < L; ++l) {
-        bits |= reinterpret_cast<uintptr_t>(act[l]) | reinterpret_cast<uintptr_t>(grad_act[l]);
+        if (!tiered) bits |= reinterpret_cast<uintptr_t>(act[l]) | reinterpret_cast<uintptr_t>(grad_act[l]);
         for (int j = 0; j < 2; ++j)
             bits |= reinterpret_cast<uintptr_t>(weights[3 * l + j]) | reinterpret_cast<uintptr_t>(grad_w[3 * l + j]);
     }
@@ -1150,14 +1154,16 @@ gnn_status gnn_bind(gnn_ctx* c, const void* feat, void* const* act, void* const*
     gnn_status st = ensure_device(c);
     if (st != GNN_OK) return st;
     if (c->fuse_gather && !c->streaming() && c->model != GNN_GAT && (st = ensure_global_columns(c)) != GNN_OK) return st;
-    c->feat = (const char*)feat;
+    c->feat = tiered ? nullptr : (const char*)feat;
     c->act.assign((size_t)L, nullptr);
     c->gact.assign((size_t)L, nullptr);
     c->w.assign((size_t)3 * L, nullptr);
     c->gw.assign((size_t)3 * L, nullptr);
     for (int32_t l = 0; l < L; ++l) {
-        c->act[(size_t)l] = (char*)act[l];
-        c->gact[(size_t)l] = (float*)grad_act[l];
+        if (!tiered) {
+            c->act[(size_t)l] = (char*)act[l];
+            c->gact[(size_t)l] = (float*)grad_act[l];
+        }
         for (int j = 0; j < 3; ++j) {
             c->w[(size_t)(3 * l + j)] = (const char*)weights[3 * l + j];
             c->gw[(size_t)(3 * l + j)] = (float*)grad_w[3 * l + j];
@@ -1757,6 +1763,63 @@ gnn_status gnn_get_profile(const gnn_ctx* c, double* ms, int64_t* launches)
         ms[i] = c->prof_ms[i];
         launches[i] = c->prof_launches[i];
     }
+    return GNN_OK;
+}
+
+gnn_status gnn_storage_open(gnn_ctx* c, const char* dir, int64_t host_budget_bytes)
+{
+    if (!c || !dir) return GNN_EINVAL;
+    if (!c->built) return c->fail(GNN_ESTATE, "gnn_storage_open before gnn_build_partitions");
+    if (!c->streaming())
+        return c->fail(GNN_ESTATE, "the storage tier belongs to the streaming schedule: create the context with hbm_budget_bytes > 0");
+    c->bound = false;                  // feat / act / grad_act of an earlier gnn_bind are no longer used
+    return tier_open(c, dir, host_budget_bytes);
+}
+
+gnn_status gnn_storage_close(gnn_ctx* c)
+{
+    if (!c) return GNN_EINVAL;
+    if (c->tier) {
+        (void)hipDeviceSynchronize();
+        tier_close(c);
+        c->bound = false;
+    }
+    return GNN_OK;
+}
+
+static gnn_status storage_array(gnn_ctx* c, int32_t kind, int32_t layer, int* id)
+{
+    if (!c->tier) return c->fail(GNN_ESTATE, "no storage tier is open (gnn_storage_open)");
+    *id = (kind == 0 || kind == 1) ? tier_array_id(c, kind, layer) : -1;
+    if (*id < 0) return c->fail(GNN_EINVAL, "no such array: kind 0 takes layers 0..L, kind 1 layers 1..L");
+    return GNN_OK;
+}
+
+gnn_status gnn_storage_write(gnn_ctx* c, int32_t kind, int32_t layer, const void* src_host)
+{
+    if (!c || !src_host) return GNN_EINVAL;
+    int id;
+    gnn_status st = storage_array(c, kind, layer, &id);
+    if (st != GNN_OK) return st;
+    if (hipDeviceSynchronize() != hipSuccess) (void)hipGetLastError();
+    return tier_write(c, id, src_host);
+}
+
+gnn_status gnn_storage_read(gnn_ctx* c, int32_t kind, int32_t layer, void* dst_host)
+{
+    if (!c || !dst_host) return GNN_EINVAL;
+    int id;
+    gnn_status st = storage_array(c, kind, layer, &id);
+    if (st != GNN_OK) return st;
+    if (hipDeviceSynchronize() != hipSuccess) (void)hipGetLastError();
+    return tier_read(c, id, dst_host);
+}
+
+gnn_status gnn_get_storage_stats(const gnn_ctx* c, gnn_storage_stats* out)
+{
+    if (!c || !out) return GNN_EINVAL;
+    if (!c->tier) return c->fail(GNN_ESTATE, "no storage tier is open (gnn_storage_open)");
+    tier_get_stats(c, out);
     return GNN_OK;
 }
 

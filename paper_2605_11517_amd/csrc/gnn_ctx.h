@@ -71,6 +71,7 @@ struct Workspace {  // byte offsets into `scratch`
 };
 
 struct StreamEngine;  // streaming.cpp
+struct StorageTier;  // storage_tier.cpp
 
 }  // namespace gnnmi
 
@@ -160,6 +161,7 @@ struct gnn_ctx {
     std::vector<int32_t> bwd_done;      // per layer: partitions finished since gnn_loss
     bool loss_done = false;
     gnnmi::StreamEngine* stream_engine = nullptr;
+    gnnmi::StorageTier* tier = nullptr;    // storage below host memory: feat / act / gact then point into its pool
     // profiling
     int prof = 0;                       // 0 off, 1 every kernel class, 2 the aggregation classes only
     std::vector<hipEvent_t> events;
@@ -279,6 +281,20 @@ void gat_bwd_begin(gnn_ctx* c, int32_t layer, hipStream_t s);
 void gat_layer_bwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s);
 void gat_transform_bwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s);
 void collect_profile(gnn_ctx* c);
+
+// storage_tier.cpp: whole per-layer arrays in a pinned pool backed by files.  Array ids: 0..L =
+// A^0..A^L, L + l = grad A^l.
+gnn_status tier_open(gnn_ctx* c, const char* dir, int64_t host_budget_bytes);
+void tier_close(gnn_ctx* c);
+int tier_array_id(const gnn_ctx* c, int kind, int layer);    // -1: no such array
+int64_t tier_array_bytes(const gnn_ctx* c, int id);
+// Makes the arrays need[0..nneed) resident (bit i of overwrite_mask: need[i] is overwritten whole,
+// not read) and sets feat / act / gact of the context; next[]: what the phase after reads.  The
+// device must be idle with respect to every array that is not in `need`.
+gnn_status tier_prepare(gnn_ctx* c, const int* need, int nneed, unsigned overwrite_mask, const int* next, int nnext);
+gnn_status tier_write(gnn_ctx* c, int id, const void* src);
+gnn_status tier_read(gnn_ctx* c, int id, void* dst);
+void tier_get_stats(const gnn_ctx* c, gnn_storage_stats* out);
 
 // streaming.cpp
 gnn_status stream_engine_create(gnn_ctx* c);

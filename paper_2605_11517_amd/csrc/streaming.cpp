@@ -29,6 +29,7 @@
 #include <climits>
 #include <cstdint>
 #include <cstring>
+#include <initializer_list>
 #include <memory>
 
 #include "gnn_ctx.h"
@@ -836,10 +837,35 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
         return GNN_OK;
     };
 
+    // Storage tier below host memory: before a phase enqueues anything, the arrays it reads or
+    // writes are brought into the pinned pool (and the least recently used others leave it).  The
+    // device must have finished with whatever may leave, so the phase boundary becomes a host
+    // synchronisation; arrays may come back at another address, so the host pointers kept by whole
+    // arrays in the HBM pool are renewed (those arrays are clean at a phase boundary).
+    auto tier_phase = [&](std::initializer_list<int> need, unsigned overwrite_mask,
+                          std::initializer_list<int> next) -> gnn_status {
+        if (!c->tier) return GNN_OK;
+        GNN_HIP(hipStreamSynchronize(s));
+        GNN_HIP(hipStreamSynchronize(E.d2h));
+        GNN_HIP(hipStreamSynchronize(E.h2d));
+        std::vector<int> nd, nx;
+        for (int id : need) if (id >= 0) nd.push_back(id);
+        for (int id : next) if (id >= 0) nx.push_back(id);
+        gnn_status t_st = tier_prepare(c, nd.data(), (int)nd.size(), overwrite_mask, nx.data(), (int)nx.size());
+        if (t_st != GNN_OK) return t_st;
+        for (auto& r : E.arrays)
+            r->bc.host = r->kind == ARR_ACT ? act_host(r->layer) : (char*)c->gact[(size_t)r->layer - 1];
+        return GNN_OK;
+    };
+    auto act_id = [&](int32_t layer) { return layer >= 0 && layer <= L ? (int)layer : -1; };
+    auto grad_id = [&](int32_t layer) { return layer >= 1 && layer <= L ? (int)(L + layer) : -1; };
+
     // ---------------------------------------------------------------------------- forward
     for (int32_t l = 1; l <= L; ++l) {
         const int32_t dout = c->dims[(size_t)l];
         const Key keep[2] = {{ARR_ACT, l - 1}, {ARR_ACT, l}};
+        // reads A^{l-1}, writes every row of A^l
+        if ((st = tier_phase({act_id(l - 1), act_id(l)}, 2u, {})) != GNN_OK) return st;
         if (c->transform_first(l)) {
             // Transform-first layer: sweep 1 computes H_p = A_p^{l-1} W for every partition into the
             // whole-graph buffer, sweep 2 gathers and aggregates rows of H.  No partition needs
@@ -940,6 +966,8 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
     {
         const int32_t C = c->dims[(size_t)L];
         const Key keep[3] = {{ARR_ACT, L}, {ARR_GRAD, L}, {ARR_ACT, L - 1}};
+        // reads the logits, writes every row of grad A^L; the backward pass of layer L reads A^{L-1} next
+        if ((st = tier_phase({act_id(L), grad_id(L)}, 2u, {act_id(L - 1)})) != GNN_OK) return st;
         Resident* logits = find_array(E, keep[0]);
         Resident* gout = nullptr;
         // kept for the backward pass of layer L only if there is free room for it
@@ -993,6 +1021,10 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
         const Key keep[4] = {{ARR_GRAD, l - 1}, {ARR_ACT, l - 1}, {ARR_GRAD, l}, {ARR_ACT, l}};
         const int64_t a_slot = act_slot_bytes(l - 1), g_slot = grad_slot_bytes(l - 1);
         const int64_t a_blk = round256(a_slot), g_blk = round256(g_slot);      // slots of a block cache
+        // reads grad A^l, A^l (hidden layers) and A^{l-1}, writes every row of grad A^{l-1}; the
+        // layer below reads A^{l-2} next
+        if ((st = tier_phase({grad_id(l), act_id(l - 1), l < L ? act_id(l) : -1, grad_id(l - 1)},
+                             (l >= 2 ? (l < L ? 8u : 4u) : 0u), {act_id(l - 2)})) != GNN_OK) return st;
         if (c->transform_first(l)) {
             // Transform-first layer: sweep 1 scatter-accumulates S_p^T dY_p into the whole-graph
             // buffer grad H (so no block of grad A^{l-1} is ever cycled through a cache), sweep 2

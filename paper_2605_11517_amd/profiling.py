@@ -73,8 +73,9 @@ def _per_kernel(path, counter):
     for r in csv.DictReader(open(path)):
         if r["Counter_Name"] != counter:
             continue
-        e = out.setdefault(short_name(r["Kernel_Name"]), {"kib": 0.0, "launches": 0, "ns": 0})
+        e = out.setdefault(short_name(r["Kernel_Name"]), {"kib": 0.0, "launches": 0, "ns": 0, "max_kib": 0.0})
         e["kib"] += float(r["Counter_Value"])
+        e["max_kib"] = max(e["max_kib"], float(r["Counter_Value"]))
         e["launches"] += 1
         e["ns"] += int(r["End_Timestamp"]) - int(r["Start_Timestamp"])
     return out
@@ -89,7 +90,7 @@ def summarize_pmc(fetch_dir: str, write_dir: str, out_path: str, command: str, c
         best = 0.0
         for name, e in table.items():
             if "copyBuffer" in name or "copy" in name.lower():
-                best = max(best, e["kib"])
+                best = max(best, e["max_kib"])
         return (GIB / 1024.0) / best if best > 0 else 1.0
 
     fs, ws = copy_scale(fetch), copy_scale(write)

@@ -523,6 +523,89 @@ def test_streaming_schedule_is_bit_identical_to_resident(case):
     assert e.value.status == 5
 
 
+TIER_CASES = [
+    # (config, dtype, layer order, HBM budget in multiples of the minimum, extra whole arrays of host pool)
+    ("mini_sage", "f32", "aggregate", 2.5, 0),          # host pool of exactly one backward layer's arrays
+    ("mini_sage", "f32", "auto", 40.0, 0),              # transform-first layers, whole arrays in HBM
+    ("mini_gcn_directed", "f32", "aggregate", 1.0, 1),  # two-slot HBM caches: rows read from the pool directly
+    ("mini_gcn_directed", "bf16", "aggregate", 3.0, 0),
+    ("tiny", "f32", "aggregate", 100.0, 100),           # everything fits on both levels
+]
+
+
+@pytest.mark.parametrize("case", TIER_CASES, ids=lambda c: "%s-%s-%s-x%g-+%d" % c)
+def test_storage_tier_below_host_memory_is_bit_identical_to_resident(case, tmp_path):
+    """gnn_storage_open: the per-layer arrays live in files, whole arrays are cached in a pinned host
+    pool (least recently used ones leave when a phase needs room), the streaming schedule runs on
+    top.  Same kernels on the same blocks: losses and every tensor must be the resident bits."""
+    name, dtype, order, factor, extra = case
+    say("case storage tier %s" % (case,))
+    from paper_2605_11517_amd import GnnError, Session
+    from synth import to_bf16_grid
+    cfg, rowptr, colidx = make_config(name)
+    n, dims = cfg["n"], cfg["dims"]
+    L = len(dims) - 1
+    X, y, m, w = make_inputs(cfg, n)
+    if dtype == "bf16":
+        X = to_bf16_grid(X)
+    common = dict(dtype=dtype, layer_order=order)
+    res = Session(cfg["model"], dims, rowptr, colidx, cfg["k"], cfg["part"], cfg["seed"], X, w, y, m, **common)
+    loss_res = res.epoch()
+    r_res = res.results()
+    st = res.ctx.get_stats()
+    del res
+    es = 2 if dtype == "bf16" else 4
+    rnd = lambda b: (b + 255) // 256 * 256
+    hbm_min = 2 * rnd(st["max_own"] * max(dims) * es) + 2 * rnd(st["max_own"] * max(dims) * 4)
+    hp = 0
+    if order == "auto":                               # room for the whole-graph buffer of such layers
+        hp = rnd(n * ((max(dims[1:]) + 3) // 4 * 4) * 4) * 2 + 4 * rnd(st["max_own"] * max(dims) * 4) * (cfg["k"] + 2)
+    a_bytes = lambda l: n * dims[l] * (4 if l == L else es)       # A^l (the logits are fp32)
+    g_bytes = lambda l: n * dims[l] * 4
+    need = max(g_bytes(l) + a_bytes(l) + a_bytes(l - 1) + (g_bytes(l - 1) if l >= 2 else 0) for l in range(1, L + 1))
+    need += 4 * 4096
+    total = sum(a_bytes(l) for l in range(L + 1)) + sum(g_bytes(l) for l in range(1, L + 1))
+    args = (cfg["model"], dims, rowptr, colidx, cfg["k"], cfg["part"], cfg["seed"], X, w, y, m)
+    # a pool that cannot hold one backward layer's arrays is refused
+    with pytest.raises(GnnError) as e:
+        Session(*args, hbm_budget_bytes=int(hbm_min * factor) + hp, storage_dir=str(tmp_path),
+                host_budget_bytes=need - 8192, **common)
+    assert e.value.status == 2
+    host_budget = need + extra * (max(g_bytes(l) for l in range(1, L + 1)) + 4096)
+    s = Session(*args, hbm_budget_bytes=int(hbm_min * factor) + hp, storage_dir=str(tmp_path),
+                host_budget_bytes=host_budget, **common)
+    if order == "auto":
+        assert any(s.ctx.layer_is_transform_first(l) for l in range(1, L + 1))
+    for rep in range(2):
+        assert s.epoch() == loss_res
+        got = s.results()
+        for key in ("act", "gact", "gW", "gWs", "gb"):
+            for l, (a, b) in enumerate(zip(got[key], r_res[key])):
+                if a is None:
+                    assert b is None
+                    continue
+                assert np.array_equal(a, b), (rep, key, l)
+    tst = s.ctx.get_storage_stats()
+    say("  storage stats %s (arrays %d bytes, pool %d)" % (tst, total, host_budget))
+    assert tst["host_pool_bytes"] >= need - 4096 and tst["array_bytes"] >= total
+    if host_budget >= total + 16 * 4096:
+        # everything stays in the pool: the files are read for the features only
+        assert tst["evictions"] == 0 and tst["writebacks"] == 0
+        assert tst["loads"] == 1 and tst["bytes_read"] >= a_bytes(0)
+    else:
+        assert tst["evictions"] > 0 and tst["writebacks"] > 0 and tst["loads"] > 1
+        assert tst["bytes_written"] > 0 and tst["bytes_read"] > a_bytes(0)
+    # the entry points of the tier refuse what they cannot do
+    with pytest.raises(GnnError) as e:
+        s.ctx.storage_read(0, L + 1, 0)
+    assert e.value.status == 1
+    s.ctx.storage_close()
+    with pytest.raises(GnnError) as e:
+        s.ctx.get_storage_stats()
+    assert e.value.status == 4
+    assert not any(f.name.startswith("array_") for f in tmp_path.iterdir())
+
+
 @pytest.mark.parametrize("name,dims,extra", [
     ("mini_sage", (100, 256, 256, 47), 1.0),            # hidden GraphSAGE layer takes its dY rows twice; padded 48-wide output
     ("mini_sage", (100, 256, 256, 47), 3.0),
