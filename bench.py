@@ -212,7 +212,10 @@ def run_workload(name, args, steps, warmup, want_cpu):
     s = Session(model, dims, rowptr, colidx, cfg["k"], cfg["part"], cfg["seed"], X, w, y, m,
                 dtype=cfg["dtype"], hbm_budget_bytes=budget,
                 layer_order=args.layer_order, fuse_gather=not args.staged_gather,
-                masked_backward=not args.full_backward, progress=lambda msg: log("  " + msg))
+                masked_backward=not args.full_backward, storage_dir=args.storage_dir,
+                host_budget_bytes=int(args.host_budget_gb * 2 ** 30), progress=lambda msg: log("  " + msg))
+    if args.storage_dir and args.storage_drop_results:
+        s.ctx.storage_keep_results(False)
     gather_fused = s.ctx.gather_is_fused()
     m_entries, m_rows = s.ctx.masked_backward_size()
     masked = (m_entries, m_rows, int((m != 0).sum())) if m_rows or m_entries else None
@@ -286,6 +289,7 @@ def run_workload(name, args, steps, warmup, want_cpu):
     log("[%s] epoch %.2f ms, loss %.5f" % (name, ms_per_step, loss))
 
     stream_stats = s.ctx.get_stream_stats() if budget else None
+    storage_stats = s.ctx.get_storage_stats() if args.storage_dir else None
 
     # the same epoch with every layer in the paper's order (aggregate, then transform; regather
     # and recompute in the backward pass of every layer): context, not the headline
@@ -449,6 +453,12 @@ def run_workload(name, args, steps, warmup, want_cpu):
                         "one source row read per operator entry",
             }
         out["profiled_ms_per_step"] = sum(v[0] for v in breakdown.values())
+    if storage_stats is not None:
+        # file traffic of the whole run (placement of the features, warm-up and timed epochs)
+        storage_stats["epochs_run"] = warmup + steps + (1 if not args.no_profile else 0)
+        out["storage"] = storage_stats
+        out["config"]["workload"] += " (storage tier: %.3g GiB host pool over %.3g GiB of arrays)" % (
+            storage_stats["host_pool_bytes"] / 2 ** 30, storage_stats["array_bytes"] / 2 ** 30)
     if stream_stats is not None:
         stream_stats["pcie_GBps"] = (stream_stats["h2d_bytes"] + stream_stats["d2h_bytes"]) / (ms_per_step * 1e-3) / 1e9
         out["streaming"] = stream_stats
@@ -495,6 +505,13 @@ def main():
     ap.add_argument("--hbm-budget-gb", type=float, default=0.0,
                     help="> 0: run the streaming schedule (activations and gradients in pinned host "
                          "memory) with this much HBM for the partition-block caches")
+    ap.add_argument("--storage-dir", default=None,
+                    help="streaming schedule with the storage tier: per-layer arrays in files of this directory")
+    ap.add_argument("--storage-drop-results", action="store_true",
+                    help="storage tier: arrays the epoch is done with are dropped instead of written back "
+                         "(a training loop reads only the weight gradients)")
+    ap.add_argument("--host-budget-gb", type=float, default=0.0,
+                    help="size of the storage tier's pinned host pool in GiB")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (a dispatch of known "
                          "size, used to scale hardware byte counters)")

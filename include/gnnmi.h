@@ -452,6 +452,14 @@ gnn_status gnn_get_stream_stats(const gnn_ctx *ctx, gnn_stream_stats *out);
  * cannot be created; GNN_EHIP for a failed read or write (message in gnn_last_error). */
 gnn_status gnn_storage_open(gnn_ctx *ctx, const char *dir, int64_t host_budget_bytes);
 gnn_status gnn_storage_close(gnn_ctx *ctx);
+/* What happens to an array that leaves the pool after the epoch has read it for the last time
+ * (A^l and grad A^l once layer l's backward pass has run, the logits once the loss has).
+ * on = 1 (default): it is written to its file like any other, so gnn_storage_read returns every
+ * activation and gradient of the last epoch.  on = 0: it is dropped - a training loop reads only
+ * the weight gradients, and the next epoch overwrites these arrays before it reads them;
+ * gnn_storage_read of a dropped array returns zeros.  (The contents an epoch finds in these
+ * arrays when it starts are never written back in either mode.) */
+gnn_status gnn_storage_keep_results(gnn_ctx *ctx, int32_t on);
 gnn_status gnn_storage_write(gnn_ctx *ctx, int32_t kind, int32_t layer, const void *src_host);
 gnn_status gnn_storage_read(gnn_ctx *ctx, int32_t kind, int32_t layer, void *dst_host);
 typedef struct {
@@ -462,6 +470,7 @@ typedef struct {
     int64_t evictions, writebacks;
     int64_t bytes_read, bytes_written; /* file traffic since gnn_storage_open */
     int64_t compactions;     /* times the arrays in the pool were moved together to join free room */
+    int64_t dropped;         /* arrays that left the pool unwritten (gnn_storage_keep_results(0)) */
 } gnn_storage_stats;
 gnn_status gnn_get_storage_stats(const gnn_ctx *ctx, gnn_storage_stats *out);
 

@@ -56,7 +56,7 @@ def make_optimizer(kind="adam", lr=0.01, beta1=0.9, beta2=0.999, eps=1e-8, weigh
 
 class StorageStats(C.Structure):
     _fields_ = [(n_, C.c_int64) for n_ in ("host_pool_bytes", "array_bytes", "loads", "hits", "prefetched",
-                                           "evictions", "writebacks", "bytes_read", "bytes_written", "compactions")]
+                                           "evictions", "writebacks", "bytes_read", "bytes_written", "compactions", "dropped")]
 
 
 class StreamStats(C.Structure):
@@ -115,6 +115,7 @@ def load_library():
         "gnn_get_stream_stats": [vp, P(StreamStats)],
         "gnn_storage_open": [vp, C.c_char_p, i64],
         "gnn_storage_close": [vp],
+        "gnn_storage_keep_results": [vp, i32],
         "gnn_storage_write": [vp, i32, i32, vp],
         "gnn_storage_read": [vp, i32, i32, vp],
         "gnn_get_storage_stats": [vp, P(StorageStats)],
@@ -325,6 +326,9 @@ class Context:
 
     def storage_open(self, directory, host_budget_bytes):
         self._check(self.lib.gnn_storage_open(self.h, os.fsencode(directory), int(host_budget_bytes)))
+
+    def storage_keep_results(self, on):
+        self._check(self.lib.gnn_storage_keep_results(self.h, 1 if on else 0))
 
     def storage_close(self):
         self._check(self.lib.gnn_storage_close(self.h))

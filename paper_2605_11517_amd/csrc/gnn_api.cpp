@@ -1787,6 +1787,15 @@ gnn_status gnn_storage_close(gnn_ctx* c)
     return GNN_OK;
 }
 
+gnn_status gnn_storage_keep_results(gnn_ctx* c, int32_t on)
+{
+    if (!c) return GNN_EINVAL;
+    if (!c->tier) return c->fail(GNN_ESTATE, "no storage tier is open (gnn_storage_open)");
+    if (on != 0 && on != 1) return c->fail(GNN_EINVAL, "gnn_storage_keep_results takes 0 or 1");
+    tier_keep_results(c, on == 1);
+    return GNN_OK;
+}
+
 static gnn_status storage_array(gnn_ctx* c, int32_t kind, int32_t layer, int* id)
 {
     if (!c->tier) return c->fail(GNN_ESTATE, "no storage tier is open (gnn_storage_open)");

@@ -291,7 +291,11 @@ int64_t tier_array_bytes(const gnn_ctx* c, int id);
 // Makes the arrays need[0..nneed) resident (bit i of overwrite_mask: need[i] is overwritten whole,
 // not read) and sets feat / act / gact of the context; next[]: what the phase after reads.  The
 // device must be idle with respect to every array that is not in `need`.
-gnn_status tier_prepare(gnn_ctx* c, const int* need, int nneed, unsigned overwrite_mask, const int* next, int nnext);
+// dead[]: arrays that nothing reads again in this epoch once the phase has run.
+gnn_status tier_prepare(gnn_ctx* c, const int* need, int nneed, unsigned overwrite_mask, const int* next, int nnext,
+                        const int* dead, int ndead);
+void tier_epoch_begin(gnn_ctx* c);             // the arrays of the last epoch (all but the features) are stale
+void tier_keep_results(gnn_ctx* c, bool keep); // false: arrays the epoch is done with are dropped, not written back
 gnn_status tier_write(gnn_ctx* c, int id, const void* src);
 gnn_status tier_read(gnn_ctx* c, int id, void* dst);
 void tier_get_stats(const gnn_ctx* c, gnn_storage_stats* out);

@@ -44,6 +44,7 @@ struct TierArray {
     bool dirty = false;         // host copy newer than the file
     bool on_disk = false;       // the file holds the array
     bool busy = false;          // the helper thread is loading it
+    bool dead = false;          // not read again before the next epoch overwrites it
     int64_t last_use = 0;
 };
 
@@ -54,12 +55,14 @@ struct StorageTier {
     std::vector<std::pair<int64_t, int64_t>> free_list;   // (offset, bytes), ascending, coalesced
     std::vector<TierArray> arr;                           // 0..L: A^l, L+1..2L: grad A^l
     int64_t tick = 0;
+    bool keep_results = true;   // write arrays back even when the epoch itself will not read them again
     gnn_storage_stats stats{};
     // helper thread: loads the arrays named in `wanted` when that needs no eviction
     std::mutex mu;
     std::condition_variable cv;
     std::thread worker;
     std::vector<int> wanted;
+    std::vector<int> cur_need;  // arrays of the running phase: the helper thread leaves them alone
     bool stop = false, working = false;
     std::string worker_error;
 };
@@ -134,6 +137,12 @@ bool read_all(int fd, char* dst, int64_t bytes, std::string& err)
 bool evict(StorageTier& T, int id, std::string& err)
 {
     TierArray& a = T.arr[(size_t)id];
+    if (a.dirty && a.dead && !T.keep_results) {
+        // nobody will read it: the next epoch overwrites it
+        a.dirty = false;
+        a.on_disk = false;
+        ++T.stats.dropped;
+    }
     if (a.dirty) {
         if (!write_all(a.fd, T.pool + a.off, a.bytes, err)) return false;
         a.dirty = false;
@@ -147,21 +156,27 @@ bool evict(StorageTier& T, int id, std::string& err)
     return true;
 }
 
-// Room for array `id` (lock held).  `keep`: arrays that must stay.  may_evict = false: free room only.
-bool make_room(StorageTier& T, int id, const std::vector<int>& keep, bool may_evict, std::string& err)
+// Room for array `id` (lock held).  `keep`: arrays that must stay.  background = true (the helper
+// thread, while the device works on the arrays in `keep`): only arrays the epoch is done with may
+// leave and nothing is moved; a.off stays -1 when that is not enough.
+bool make_room(StorageTier& T, int id, const std::vector<int>& keep, bool background, std::string& err)
 {
     TierArray& a = T.arr[(size_t)id];
     for (;;) {
         a.off = tier_alloc(T, a.bytes);
         if (a.off >= 0) return true;
-        if (!may_evict) return true;            // (a.off stays -1)
         int victim = -1;
         for (int j = 0; j < (int)T.arr.size(); ++j) {
             const TierArray& v = T.arr[(size_t)j];
             if (v.off < 0 || v.busy || j == id) continue;
+            if (background && !v.dead) continue;
             if (std::find(keep.begin(), keep.end(), j) != keep.end()) continue;
-            if (victim < 0 || v.last_use < T.arr[(size_t)victim].last_use) victim = j;
+            // arrays the epoch is done with go first, then the least recently used
+            if (victim < 0 || (v.dead && !T.arr[(size_t)victim].dead) ||
+                (v.dead == T.arr[(size_t)victim].dead && v.last_use < T.arr[(size_t)victim].last_use))
+                victim = j;
         }
+        if (victim < 0 && background) return true;      // (a.off stays -1)
         if (victim < 0) {
             // nothing left to evict: if the free room is enough but scattered, move the arrays
             // together (the device is idle and the helper thread is not reading)
@@ -202,7 +217,11 @@ void worker_main(StorageTier* T)
         TierArray& a = T->arr[(size_t)id];
         if (a.off >= 0 || !a.on_disk || a.busy) continue;
         std::string err;
-        if (!make_room(*T, id, {}, false, err) || a.off < 0) continue;   // no free room: the phase will load it
+        if (!make_room(*T, id, T->cur_need, true, err)) {
+            T->worker_error = err;
+            continue;
+        }
+        if (a.off < 0) continue;                 // no room: the phase will load it
         a.busy = true;
         T->working = true;
         char* dst = T->pool + a.off;
@@ -217,6 +236,7 @@ void worker_main(StorageTier* T)
             T->stats.bytes_read += bytes;
             ++T->stats.loads;
             ++T->stats.prefetched;
+            a.dead = false;
             a.last_use = ++T->tick;
         } else {
             tier_free(*T, a.off, a.bytes);
@@ -323,7 +343,29 @@ static void publish(gnn_ctx* c)
     }
 }
 
-gnn_status tier_prepare(gnn_ctx* c, const int* need, int nneed, unsigned overwrite_mask, const int* next, int nnext)
+void tier_keep_results(gnn_ctx* c, bool keep)
+{
+    std::lock_guard<std::mutex> lk(c->tier->mu);
+    c->tier->keep_results = keep;
+}
+
+// A new epoch overwrites every array but the features before it reads them: what the last epoch
+// left in them need not be written anywhere.
+void tier_epoch_begin(gnn_ctx* c)
+{
+    StorageTier& T = *c->tier;
+    std::unique_lock<std::mutex> lk(T.mu);
+    T.wanted.clear();
+    T.cv.wait(lk, [&] { return !T.working; });
+    for (size_t i = 1; i < T.arr.size(); ++i) {
+        T.arr[i].dirty = false;
+        T.arr[i].on_disk = false;
+        T.arr[i].dead = true;
+    }
+}
+
+gnn_status tier_prepare(gnn_ctx* c, const int* need, int nneed, unsigned overwrite_mask, const int* next, int nnext,
+                        const int* dead, int ndead)
 {
     StorageTier& T = *c->tier;
     std::unique_lock<std::mutex> lk(T.mu);
@@ -341,7 +383,7 @@ gnn_status tier_prepare(gnn_ctx* c, const int* need, int nneed, unsigned overwri
         TierArray& a = T.arr[(size_t)id];
         const bool overwrite = (overwrite_mask >> i) & 1u;
         if (a.off < 0) {
-            if (!make_room(T, id, keep, true, err)) return c->fail(GNN_ENOMEM, "storage tier: " + err);
+            if (!make_room(T, id, keep, false, err)) return c->fail(GNN_ENOMEM, "storage tier: " + err);
             if (!overwrite) {
                 if (!a.on_disk) {
                     // never written: the schedule reads an array only after a phase produced it
@@ -359,8 +401,12 @@ gnn_status tier_prepare(gnn_ctx* c, const int* need, int nneed, unsigned overwri
             a.dirty = true;
             a.on_disk = false;
         }
+        a.dead = false;
         a.last_use = ++T.tick;
     }
+    // (takes effect when the next phase asks for room: by then this phase has run)
+    for (int i = 0; i < ndead; ++i) T.arr[(size_t)dead[i]].dead = true;
+    T.cur_need = keep;
     publish(c);
     // the helper thread brings in what the next phase reads, in free room only
     for (int i = nnext - 1; i >= 0; --i)

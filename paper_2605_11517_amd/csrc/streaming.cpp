@@ -843,15 +843,17 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
     // synchronisation; arrays may come back at another address, so the host pointers kept by whole
     // arrays in the HBM pool are renewed (those arrays are clean at a phase boundary).
     auto tier_phase = [&](std::initializer_list<int> need, unsigned overwrite_mask,
-                          std::initializer_list<int> next) -> gnn_status {
+                          std::initializer_list<int> next, std::initializer_list<int> dead) -> gnn_status {
         if (!c->tier) return GNN_OK;
         GNN_HIP(hipStreamSynchronize(s));
         GNN_HIP(hipStreamSynchronize(E.d2h));
         GNN_HIP(hipStreamSynchronize(E.h2d));
-        std::vector<int> nd, nx;
+        std::vector<int> nd, nx, dd;
         for (int id : need) if (id >= 0) nd.push_back(id);
         for (int id : next) if (id >= 0) nx.push_back(id);
-        gnn_status t_st = tier_prepare(c, nd.data(), (int)nd.size(), overwrite_mask, nx.data(), (int)nx.size());
+        for (int id : dead) if (id >= 0) dd.push_back(id);
+        gnn_status t_st = tier_prepare(c, nd.data(), (int)nd.size(), overwrite_mask, nx.data(), (int)nx.size(),
+                                       dd.data(), (int)dd.size());
         if (t_st != GNN_OK) return t_st;
         for (auto& r : E.arrays)
             r->bc.host = r->kind == ARR_ACT ? act_host(r->layer) : (char*)c->gact[(size_t)r->layer - 1];
@@ -865,7 +867,8 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
         const int32_t dout = c->dims[(size_t)l];
         const Key keep[2] = {{ARR_ACT, l - 1}, {ARR_ACT, l}};
         // reads A^{l-1}, writes every row of A^l
-        if ((st = tier_phase({act_id(l - 1), act_id(l)}, 2u, {})) != GNN_OK) return st;
+        if (l == 1 && c->tier) tier_epoch_begin(c);
+        if ((st = tier_phase({act_id(l - 1), act_id(l)}, 2u, {}, {})) != GNN_OK) return st;
         if (c->transform_first(l)) {
             // Transform-first layer: sweep 1 computes H_p = A_p^{l-1} W for every partition into the
             // whole-graph buffer, sweep 2 gathers and aggregates rows of H.  No partition needs
@@ -967,7 +970,8 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
         const int32_t C = c->dims[(size_t)L];
         const Key keep[3] = {{ARR_ACT, L}, {ARR_GRAD, L}, {ARR_ACT, L - 1}};
         // reads the logits, writes every row of grad A^L; the backward pass of layer L reads A^{L-1} next
-        if ((st = tier_phase({act_id(L), grad_id(L)}, 2u, {act_id(L - 1)})) != GNN_OK) return st;
+        // (the output layer has no activation to differentiate: the logits are not read again)
+        if ((st = tier_phase({act_id(L), grad_id(L)}, 2u, {act_id(L - 1)}, {act_id(L)})) != GNN_OK) return st;
         Resident* logits = find_array(E, keep[0]);
         Resident* gout = nullptr;
         // kept for the backward pass of layer L only if there is free room for it
@@ -1024,7 +1028,8 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
         // reads grad A^l, A^l (hidden layers) and A^{l-1}, writes every row of grad A^{l-1}; the
         // layer below reads A^{l-2} next
         if ((st = tier_phase({grad_id(l), act_id(l - 1), l < L ? act_id(l) : -1, grad_id(l - 1)},
-                             (l >= 2 ? (l < L ? 8u : 4u) : 0u), {act_id(l - 2)})) != GNN_OK) return st;
+                             (l >= 2 ? (l < L ? 8u : 4u) : 0u), {act_id(l - 2)},
+                             {grad_id(l), l < L ? act_id(l) : -1})) != GNN_OK) return st;
         if (c->transform_first(l)) {
             // Transform-first layer: sweep 1 scatter-accumulates S_p^T dY_p into the whole-graph
             // buffer grad H (so no block of grad A^{l-1} is ever cycled through a cache), sweep 2

@@ -593,8 +593,26 @@ def test_storage_tier_below_host_memory_is_bit_identical_to_resident(case, tmp_p
         assert tst["evictions"] == 0 and tst["writebacks"] == 0
         assert tst["loads"] == 1 and tst["bytes_read"] >= a_bytes(0)
     else:
-        assert tst["evictions"] > 0 and tst["writebacks"] > 0 and tst["loads"] > 1
-        assert tst["bytes_written"] > 0 and tst["bytes_read"] > a_bytes(0)
+        assert tst["evictions"] > 0 and tst["writebacks"] > 0 and tst["loads"] >= 1
+        assert tst["bytes_written"] > 0 and tst["bytes_read"] >= a_bytes(0)
+    # a training loop reads no activations or gradients: arrays the epoch is done with may be dropped
+    # instead of written back; the loss and the weight gradients stay the same bits
+    s.ctx.storage_keep_results(False)
+    before = s.ctx.get_storage_stats()
+    assert s.epoch() == loss_res and s.epoch() == loss_res
+    for key, idx in (("gW", 0), ("gWs", 1), ("gb", 2)):
+        for l in range(L):
+            g = s.gw[3 * l + idx]
+            if g is not None:
+                assert np.array_equal(g.cpu().numpy(), r_res[key][l]), (key, l)
+    after = s.ctx.get_storage_stats()
+    say("  without results kept: %d bytes written in two epochs (with: %d), %d arrays dropped, %d read ahead"
+        % (after["bytes_written"] - before["bytes_written"], before["bytes_written"] - a_bytes(0),
+           after["dropped"], after["prefetched"]))
+    if host_budget < total:
+        assert after["dropped"] > 0
+        assert after["bytes_written"] - before["bytes_written"] < before["bytes_written"]
+    s.ctx.storage_keep_results(True)
     # the entry points of the tier refuse what they cannot do
     with pytest.raises(GnnError) as e:
         s.ctx.storage_read(0, L + 1, 0)
