@@ -289,11 +289,13 @@ void tier_close(gnn_ctx* c);
 int tier_array_id(const gnn_ctx* c, int kind, int layer);    // -1: no such array
 int64_t tier_array_bytes(const gnn_ctx* c, int id);
 // Makes the arrays need[0..nneed) resident (bit i of overwrite_mask: need[i] is overwritten whole,
-// not read) and sets feat / act / gact of the context; next[]: what the phase after reads.  The
-// device must be idle with respect to every array that is not in `need`.
+// not read) and sets feat / act / gact of the context; next[]: what the phase after reads.
 // dead[]: arrays that nothing reads again in this epoch once the phase has run.
+// device_idle: the caller has waited for the device since the last phase (required whenever
+// tier_needs_io says that something has to be read, evicted or moved).
+bool tier_needs_io(gnn_ctx* c, const int* need, int nneed);
 gnn_status tier_prepare(gnn_ctx* c, const int* need, int nneed, unsigned overwrite_mask, const int* next, int nnext,
-                        const int* dead, int ndead);
+                        const int* dead, int ndead, bool device_idle);
 void tier_epoch_begin(gnn_ctx* c);             // the arrays of the last epoch (all but the features) are stale
 void tier_keep_results(gnn_ctx* c, bool keep); // false: arrays the epoch is done with are dropped, not written back
 gnn_status tier_write(gnn_ctx* c, int id, const void* src);

@@ -63,6 +63,7 @@ struct StorageTier {
     std::thread worker;
     std::vector<int> wanted;
     std::vector<int> cur_need;  // arrays of the running phase: the helper thread leaves them alone
+    bool device_idle_at_phase_start = false;   // else the device may still read arrays of the phase before
     bool stop = false, working = false;
     std::string worker_error;
 };
@@ -169,7 +170,7 @@ bool make_room(StorageTier& T, int id, const std::vector<int>& keep, bool backgr
         for (int j = 0; j < (int)T.arr.size(); ++j) {
             const TierArray& v = T.arr[(size_t)j];
             if (v.off < 0 || v.busy || j == id) continue;
-            if (background && !v.dead) continue;
+            if (background && (!v.dead || !T.device_idle_at_phase_start)) continue;
             if (std::find(keep.begin(), keep.end(), j) != keep.end()) continue;
             // arrays the epoch is done with go first, then the least recently used
             if (victim < 0 || (v.dead && !T.arr[(size_t)victim].dead) ||
@@ -364,13 +365,27 @@ void tier_epoch_begin(gnn_ctx* c)
     }
 }
 
-gnn_status tier_prepare(gnn_ctx* c, const int* need, int nneed, unsigned overwrite_mask, const int* next, int nnext,
-                        const int* dead, int ndead)
+// Whether tier_prepare for these arrays would read, evict or move anything (then the device must
+// be idle first); stops the helper thread's read-ahead as a side effect.
+bool tier_needs_io(gnn_ctx* c, const int* need, int nneed)
 {
     StorageTier& T = *c->tier;
     std::unique_lock<std::mutex> lk(T.mu);
     T.wanted.clear();
     T.cv.wait(lk, [&] { return !T.working; });
+    for (int i = 0; i < nneed; ++i)
+        if (T.arr[(size_t)need[i]].off < 0) return true;
+    return false;
+}
+
+gnn_status tier_prepare(gnn_ctx* c, const int* need, int nneed, unsigned overwrite_mask, const int* next, int nnext,
+                        const int* dead, int ndead, bool device_idle)
+{
+    StorageTier& T = *c->tier;
+    std::unique_lock<std::mutex> lk(T.mu);
+    T.wanted.clear();
+    T.cv.wait(lk, [&] { return !T.working; });
+    T.device_idle_at_phase_start = device_idle;
     if (!T.worker_error.empty()) {
         const std::string msg = "storage tier: " + T.worker_error;
         T.worker_error.clear();
@@ -383,6 +398,7 @@ gnn_status tier_prepare(gnn_ctx* c, const int* need, int nneed, unsigned overwri
         TierArray& a = T.arr[(size_t)id];
         const bool overwrite = (overwrite_mask >> i) & 1u;
         if (a.off < 0) {
+            if (!device_idle) return c->fail(GNN_ESTATE, "storage tier: an array has to be brought in while the device may be busy");
             if (!make_room(T, id, keep, false, err)) return c->fail(GNN_ENOMEM, "storage tier: " + err);
             if (!overwrite) {
                 if (!a.on_disk) {

@@ -839,21 +839,27 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
 
     // Storage tier below host memory: before a phase enqueues anything, the arrays it reads or
     // writes are brought into the pinned pool (and the least recently used others leave it).  The
-    // device must have finished with whatever may leave, so the phase boundary becomes a host
-    // synchronisation; arrays may come back at another address, so the host pointers kept by whole
-    // arrays in the HBM pool are renewed (those arrays are clean at a phase boundary).
+    // device must have finished with whatever may leave, so a phase boundary at which something
+    // has to move becomes a host synchronisation; arrays may come back at another address, so the
+    // host pointers kept by whole arrays in the HBM pool are renewed (those arrays are clean at a
+    // phase boundary).
     auto tier_phase = [&](std::initializer_list<int> need, unsigned overwrite_mask,
                           std::initializer_list<int> next, std::initializer_list<int> dead) -> gnn_status {
         if (!c->tier) return GNN_OK;
-        GNN_HIP(hipStreamSynchronize(s));
-        GNN_HIP(hipStreamSynchronize(E.d2h));
-        GNN_HIP(hipStreamSynchronize(E.h2d));
         std::vector<int> nd, nx, dd;
         for (int id : need) if (id >= 0) nd.push_back(id);
         for (int id : next) if (id >= 0) nx.push_back(id);
         for (int id : dead) if (id >= 0) dd.push_back(id);
+        // only when something has to be read, evicted or moved: otherwise every array stays where
+        // it is and the phase is enqueued behind the last one as without the tier
+        const bool io = tier_needs_io(c, nd.data(), (int)nd.size());
+        if (io) {
+            GNN_HIP(hipStreamSynchronize(s));
+            GNN_HIP(hipStreamSynchronize(E.d2h));
+            GNN_HIP(hipStreamSynchronize(E.h2d));
+        }
         gnn_status t_st = tier_prepare(c, nd.data(), (int)nd.size(), overwrite_mask, nx.data(), (int)nx.size(),
-                                       dd.data(), (int)dd.size());
+                                       dd.data(), (int)dd.size(), io);
         if (t_st != GNN_OK) return t_st;
         for (auto& r : E.arrays)
             r->bc.host = r->kind == ARR_ACT ? act_host(r->layer) : (char*)c->gact[(size_t)r->layer - 1];
