@@ -181,6 +181,31 @@ def test_gather_fused_into_the_aggregation_gives_the_staged_bits(case):
         ref = aligned_backward(og, fwd, fused["act"], w, X, y, m, TOL)
         assert abs(loss1 - ref["loss"]) <= TOL * abs(ref["loss"])
         compare(fused, ref, model, tag="fused gather")
+    if order == "aggregate":
+        # stepping by hand with the fusion on: gnn_gather_boundary launches nothing but is still the
+        # call that names the (layer, partition) the next step works on
+        st = s.stream
+        L = len(dims) - 1
+        for g in s.gw:
+            if g is not None:
+                g.zero_()
+        torch.cuda.synchronize()
+        for l in range(1, L + 1):
+            for p in range(k):
+                s.ctx.gather_boundary(l, p, st)
+                s.ctx.layer_fwd(l, p, st)
+        s.ctx.loss(st)
+        for l in range(L, 0, -1):
+            for p in range(k):
+                s.ctx.gather_boundary(l, p, st)
+                s.ctx.layer_bwd(l, p, st)
+        torch.cuda.synchronize()
+        by_hand = s.results()
+        for key in ("act", "gact", "gW", "gWs", "gb"):
+            for l, (a, b) in enumerate(zip(by_hand[key], fused[key])):
+                if a is not None:
+                    assert np.array_equal(a.view(np.uint32), b.view(np.uint32)), ("by hand", key, l)
+        assert bool((s.staging == 0xFF).all())
     # and back: the staged path fills staging again
     s.set_gather_fusion(False)
     assert s.epoch() == loss0
@@ -256,6 +281,47 @@ def test_output_layer_backward_over_train_vertices_only(case):
         for l, (a, b) in enumerate(zip(again[key], got[key])):
             if a is not None:
                 assert np.array_equal(a.view(np.uint32), b.view(np.uint32)), (key, l)
+
+
+@pytest.mark.parametrize("model,dims", [("sage", (24, 48, 32, 6)), ("gcn", (32, 32, 16))])
+def test_training_with_both_schedule_switches_follows_the_plain_session(model, dims):
+    """Dropout + Adam steps with the gather fused and the output layer's backward over train
+    vertices: the same losses and weights as the plain session (the switches change no term, only
+    the grouping of a long row's additions in the masked operator), and a streaming session, where
+    both switches have no effect, still gives the resident bits."""
+    say("case training with schedule switches %s %s" % (model, dims))
+    from paper_2605_11517_amd import Session
+    n, k = 3000, 4
+    rowptr, colidx = small_graph(n, 40000, seed=83, symmetric=True, self_loops=(model == "gcn"))
+    cfg = dict(model=model, dims=dims, seed=29, train_frac=0.5)
+    X, y, m, w = make_inputs(cfg, n)
+    m = (np.random.default_rng(3).random(n) < 0.15).astype(np.uint8)
+    runs = {}
+    for name, kw in (("plain", {}), ("switched", dict(fuse_gather=True, masked_backward=True))):
+        s = Session(model, dims, rowptr, colidx, k, "lp", 5, X, w, y, m, layer_order="auto", **kw)
+        losses = s.train(4, optimizer="adam", lr=0.01, dropout=0.3, seed=17)
+        runs[name] = (losses, [t.cpu().numpy() for t in s.w if t is not None])
+        if name == "switched":
+            assert s.ctx.gather_is_fused() and s.ctx.masked_backward_size()[0] > 0
+    for a, b in zip(runs["plain"][0], runs["switched"][0]):
+        assert abs(a - b) <= 1e-6 * abs(a), (runs["plain"][0], runs["switched"][0])
+    for a, b in zip(runs["plain"][1], runs["switched"][1]):
+        assert rel_err(b, a) <= 1e-5
+    res = Session(model, dims, rowptr, colidx, k, "lp", 5, X, w, y, m)
+    loss = res.epoch()
+    ref = res.results()
+    st = res.ctx.get_stats()
+    rnd = lambda b: (b + 255) // 256 * 256
+    budget = 3 * (2 * rnd(st["max_own"] * max(dims) * 4) + 2 * rnd(st["max_own"] * max(dims) * 4))
+    stream = Session(model, dims, rowptr, colidx, k, "lp", 5, X, w, y, m, hbm_budget_bytes=budget,
+                     fuse_gather=True, masked_backward=True)
+    assert not stream.ctx.gather_is_fused() and stream.ctx.masked_backward_size() == (0, 0)
+    assert stream.epoch() == loss
+    got = stream.results()
+    for key in ("act", "gact", "gW", "gWs", "gb"):
+        for l, (a, b) in enumerate(zip(got[key], ref[key])):
+            if a is not None:
+                assert np.array_equal(a, b), (key, l)
 
 
 def test_two_epochs_are_bit_identical_and_stepping_by_hand_equals_epoch():
