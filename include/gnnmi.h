@@ -427,19 +427,23 @@ gnn_status gnn_get_stream_stats(const gnn_ctx *ctx, gnn_stream_stats *out);
 /* ---- storage tier below host memory (streaming schedule) -------------------------------- */
 
 /* The paper keeps activations and gradients on storage and caches them in host memory: whole
- * layers while they fit, whole layers evicted in least-recently-used order when they do not
- * (partition-wise cache management section; its third mode, partition-wise eviction for a layer
- * larger than host memory, is not built).  gnn_storage_open gives a context with a streaming
- * budget (hbm_budget_bytes > 0) that tier: every per-layer array (the features A^0, A^1..A^L,
- * grad A^1..grad A^L, rows in library order) gets a file in `dir` (created, and removed again by
- * gnn_storage_close / gnn_destroy), and the library allocates one pinned host pool of
- * host_budget_bytes in which it keeps whole arrays.  Before each phase of gnn_epoch (a layer's
- * forward pass, the loss, a layer's backward pass) the arrays that phase reads or writes are made
- * resident: read from their file unless the phase overwrites them completely, evicting the least
- * recently used arrays that the phase does not need (written to their file first when they
- * changed).  A helper thread reads the next phase's arrays ahead into free room.  The streaming
- * schedule itself is unchanged (HBM caches the pool's arrays block by block), so results are the
- * resident schedule's bits.
+ * layers while they fit, whole layers evicted in least-recently-used order when they do not, and
+ * partition granularity below that (partition-wise cache management section).
+ * gnn_storage_open gives a context with a streaming budget (hbm_budget_bytes > 0) that tier:
+ * every per-layer array (the features A^0, A^1..A^L, grad A^1..grad A^L, rows in library order)
+ * gets a file in `dir` (created at full size; removed again by gnn_storage_close / gnn_destroy),
+ * and the library allocates one pinned host pool of host_budget_bytes in which it keeps whole
+ * arrays.  Before each phase of gnn_epoch (a layer's forward pass, the loss, a layer's backward
+ * pass) the arrays that phase reads or writes are made resident: read from their file unless the
+ * phase overwrites them completely, evicting the least recently used arrays that the phase does
+ * not need (written to their file first when they changed).  A helper thread reads the next
+ * phase's arrays ahead.  When the pool cannot hold a phase's arrays together, room goes to the
+ * gather source first, then to the gradient being accumulated, and an array left without room
+ * is not cached in host memory at all during that phase: its partition blocks travel between
+ * file and device through small pinned buffers as the schedule loads and stores them, and are
+ * reused in the HBM block cache only.  The streaming schedule itself is unchanged (HBM caches
+ * blocks of whatever the host level holds), so results are the resident schedule's bits with any
+ * pool size.
  *
  * Call after gnn_build_partitions and before gnn_bind; gnn_bind then ignores feat, act and
  * grad_act (pass NULL).  The features go in with gnn_storage_write(ctx, 0, 0, src) and results
@@ -447,9 +451,9 @@ gnn_status gnn_get_stream_stats(const gnn_ctx *ctx, gnn_stream_stats *out);
  * memory of the caller (kind 0: A^layer, layer 0..L, storage type of the context, logits fp32;
  * kind 1: grad A^layer, layer 1..L, fp32).  Host file I/O is synchronous on the calling thread
  * apart from the helper thread's read-ahead.
- * GNN_ESTATE without partitions or without a streaming budget; GNN_ENOMEM when the pool cannot
- * hold the four arrays a backward layer touches or cannot be allocated; GNN_EINVAL when a file
- * cannot be created; GNN_EHIP for a failed read or write (message in gnn_last_error). */
+ * GNN_ESTATE without partitions or without a streaming budget; GNN_EINVAL for a pool below 4096
+ * bytes or when a file cannot be created; GNN_ENOMEM when the pool or the files cannot be
+ * allocated; GNN_EHIP for a failed read or write (message in gnn_last_error). */
 gnn_status gnn_storage_open(gnn_ctx *ctx, const char *dir, int64_t host_budget_bytes);
 gnn_status gnn_storage_close(gnn_ctx *ctx);
 /* What happens to an array that leaves the pool after the epoch has read it for the last time
@@ -471,6 +475,8 @@ typedef struct {
     int64_t bytes_read, bytes_written; /* file traffic since gnn_storage_open */
     int64_t compactions;     /* times the arrays in the pool were moved together to join free room */
     int64_t dropped;         /* arrays that left the pool unwritten (gnn_storage_keep_results(0)) */
+    int64_t bypassed;        /* (phase, array) pairs worked on in the file, block by block, for want of room */
+    int64_t bypass_bytes;    /* file bytes of those block transfers (part of bytes_read / bytes_written) */
 } gnn_storage_stats;
 gnn_status gnn_get_storage_stats(const gnn_ctx *ctx, gnn_storage_stats *out);
 

@@ -56,7 +56,7 @@ def make_optimizer(kind="adam", lr=0.01, beta1=0.9, beta2=0.999, eps=1e-8, weigh
 
 class StorageStats(C.Structure):
     _fields_ = [(n_, C.c_int64) for n_ in ("host_pool_bytes", "array_bytes", "loads", "hits", "prefetched",
-                                           "evictions", "writebacks", "bytes_read", "bytes_written", "compactions", "dropped")]
+                                           "evictions", "writebacks", "bytes_read", "bytes_written", "compactions", "dropped", "bypassed", "bypass_bytes")]
 
 
 class StreamStats(C.Structure):

@@ -296,6 +296,11 @@ int64_t tier_array_bytes(const gnn_ctx* c, int id);
 bool tier_needs_io(gnn_ctx* c, const int* need, int nneed);
 gnn_status tier_prepare(gnn_ctx* c, const int* need, int nneed, unsigned overwrite_mask, const int* next, int nnext,
                         const int* dead, int ndead, bool device_idle);
+// Arrays used without being in the pool: "virtual" host addresses and block transfers on their files.
+char* tier_virtual_base(int id);
+bool tier_decode(const void* p, int* id, int64_t* off);
+gnn_status tier_file_read(gnn_ctx* c, int id, int64_t off, void* dst, int64_t bytes);
+gnn_status tier_file_write(gnn_ctx* c, int id, int64_t off, const void* src, int64_t bytes);
 void tier_epoch_begin(gnn_ctx* c);             // the arrays of the last epoch (all but the features) are stale
 void tier_keep_results(gnn_ctx* c, bool keep); // false: arrays the epoch is done with are dropped, not written back
 gnn_status tier_write(gnn_ctx* c, int id, const void* src);

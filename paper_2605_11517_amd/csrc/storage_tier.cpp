@@ -15,8 +15,13 @@
 //     gradient a backward layer produces) is given room without being read;
 //   - the arrays of the next phase are brought in by a helper thread while the current phase
 //     computes, as long as that needs no room of an array the current phase uses.
-// The third mode of the paper's policy (partition-wise eviction for a single layer larger than
-// host memory) is not built: the pool must hold the four arrays a backward layer touches.
+// When the pool cannot hold the arrays of one phase together (the regime of the paper's third
+// mode, partition-wise eviction), the arrays that do not fit are not cached in host memory at
+// all: the phase reads and writes them partition block by partition block, straight between
+// their file and the device through a few small pinned buffers (the schedule's side: "virtual"
+// host addresses, see tier_virtual_base) - the paper's bypass path for data with little reuse in
+// host memory.  Reuse of such blocks then happens in the HBM block cache alone.  The arrays a
+// phase names first (its gather source, then the gradient it accumulates) get the room.
 //
 // All file traffic is plain pread / pwrite in large chunks on host threads; device work never
 // touches an array that is not in the pool, because the schedule asks for the arrays of a phase
@@ -45,6 +50,7 @@ struct TierArray {
     bool on_disk = false;       // the file holds the array
     bool busy = false;          // the helper thread is loading it
     bool dead = false;          // not read again before the next epoch overwrites it
+    bool bypass = false;        // used by the running phase without being in the pool
     int64_t last_use = 0;
 };
 
@@ -295,19 +301,10 @@ gnn_status tier_open(gnn_ctx* c, const char* dir, int64_t host_budget_bytes)
     c->tier = T;
     T->dir = dir;
     T->arr.resize((size_t)2 * L + 1);
-    // the widest phase: a backward layer reads grad A^l, A^l, A^{l-1} and writes grad A^{l-1}
-    int64_t need = 0;
-    for (int32_t l = 1; l <= L; ++l) {
-        int64_t b = tier_array_bytes(c, L + l) + tier_array_bytes(c, l) + tier_array_bytes(c, l - 1);
-        if (l >= 2) b += tier_array_bytes(c, L + l - 1);
-        need = std::max(need, b);
-    }
     for (size_t i = 0; i < T->arr.size(); ++i) T->arr[i].bytes = (tier_array_bytes(c, (int)i) + 4095) / 4096 * 4096;
-    need += 4 * 4096;
-    if (host_budget_bytes < need) {
+    if (host_budget_bytes < 4096) {
         tier_close(c);
-        return c->fail(GNN_ENOMEM, "gnn_storage_open: the host pool must hold the four arrays of one backward layer (" +
-                                       std::to_string(need) + " bytes)");
+        return c->fail(GNN_EINVAL, "gnn_storage_open: host_budget_bytes must be at least 4096");
     }
     T->pool_bytes = host_budget_bytes / 4096 * 4096;
     hipError_t e = hipHostMalloc((void**)&T->pool, (size_t)T->pool_bytes, hipHostMallocDefault);
@@ -326,6 +323,12 @@ gnn_status tier_open(gnn_ctx* c, const char* dir, int64_t host_budget_bytes)
             tier_close(c);
             return c->fail(GNN_EINVAL, msg);
         }
+        // full size from the start: blocks are read and written at their offsets
+        if (ftruncate(T->arr[i].fd, (off_t)T->arr[i].bytes) != 0) {
+            const std::string msg = "gnn_storage_open: " + path + ": " + std::strerror(errno);
+            tier_close(c);
+            return c->fail(GNN_ENOMEM, msg);
+        }
     }
     T->worker = std::thread(worker_main, T);
     return GNN_OK;
@@ -336,7 +339,11 @@ static void publish(gnn_ctx* c)
 {
     StorageTier& T = *c->tier;
     const int32_t L = c->L;
-    auto at = [&](int id) { return T.arr[(size_t)id].off >= 0 ? T.pool + T.arr[(size_t)id].off : nullptr; };
+    auto at = [&](int id) -> char* {
+        const TierArray& a = T.arr[(size_t)id];
+        if (a.off >= 0) return T.pool + a.off;
+        return a.bypass ? tier_virtual_base(id) : nullptr;
+    };
     c->feat = at(0);
     for (int32_t l = 1; l <= L; ++l) {
         c->act[(size_t)l - 1] = at(l);
@@ -393,13 +400,22 @@ gnn_status tier_prepare(gnn_ctx* c, const int* need, int nneed, unsigned overwri
     }
     std::vector<int> keep(need, need + nneed);
     std::string err;
+    for (TierArray& a : T.arr) a.bypass = false;
     for (int i = 0; i < nneed; ++i) {
         const int id = need[i];
         TierArray& a = T.arr[(size_t)id];
         const bool overwrite = (overwrite_mask >> i) & 1u;
         if (a.off < 0) {
             if (!device_idle) return c->fail(GNN_ESTATE, "storage tier: an array has to be brought in while the device may be busy");
-            if (!make_room(T, id, keep, false, err)) return c->fail(GNN_ENOMEM, "storage tier: " + err);
+            if (!make_room(T, id, keep, false, err)) {
+                // no room beside the arrays named before it: the phase works on its file, block by block
+                a.bypass = true;
+                ++T.stats.bypassed;
+                if (overwrite) a.on_disk = true;       // every block is written during the phase
+                a.dead = false;
+                a.last_use = ++T.tick;
+                continue;
+            }
             if (!overwrite) {
                 if (!a.on_disk) {
                     // never written: the schedule reads an array only after a phase produced it
@@ -449,7 +465,6 @@ gnn_status tier_write(gnn_ctx* c, int id, const void* src)
     }
     // straight to its file: it takes no room until a phase needs it
     if (!write_all(a.fd, (const char*)src, bytes, err)) return c->fail(GNN_EHIP, "storage tier: " + err);
-    if (a.bytes > bytes && ftruncate(a.fd, (off_t)a.bytes) != 0) return c->fail(GNN_EHIP, "storage tier: ftruncate failed");
     a.on_disk = true;
     a.dirty = false;
     T.stats.bytes_written += bytes;
@@ -475,6 +490,52 @@ gnn_status tier_read(gnn_ctx* c, int id, void* dst)
     }
     if (!read_all(a.fd, (char*)dst, bytes, err)) return c->fail(GNN_EHIP, "storage tier: " + err);
     T.stats.bytes_read += bytes;
+    return GNN_OK;
+}
+
+// Arrays that a phase uses without having them in the pool are handed to the schedule as
+// addresses in a range no allocation can lie in: 2^62 + id * 2^48 + byte offset.  The schedule
+// does its usual pointer arithmetic on them and the two copy routines below recognise them.
+char* tier_virtual_base(int id) { return reinterpret_cast<char*>((uintptr_t)1 << 62) + ((uintptr_t)id << 48); }
+
+bool tier_decode(const void* p, int* id, int64_t* off)
+{
+    const uintptr_t v = reinterpret_cast<uintptr_t>(p);
+    if (!(v >> 62)) return false;
+    *id = (int)((v >> 48) & 0x3FFF);
+    *off = (int64_t)(v & (((uintptr_t)1 << 48) - 1));
+    return true;
+}
+
+gnn_status tier_file_read(gnn_ctx* c, int id, int64_t off, void* dst, int64_t bytes)
+{
+    StorageTier& T = *c->tier;
+    TierArray& a = T.arr[(size_t)id];
+    for (int64_t done = 0; done < bytes;) {
+        const ssize_t r = pread(a.fd, (char*)dst + done, (size_t)std::min(kChunk, bytes - done), (off_t)(off + done));
+        if (r < 0 && errno == EINTR) continue;
+        if (r <= 0) return c->fail(GNN_EHIP, std::string("storage tier: pread: ") + (r < 0 ? std::strerror(errno) : "short file"));
+        done += r;
+    }
+    std::lock_guard<std::mutex> lk(T.mu);
+    T.stats.bytes_read += bytes;
+    T.stats.bypass_bytes += bytes;
+    return GNN_OK;
+}
+
+gnn_status tier_file_write(gnn_ctx* c, int id, int64_t off, const void* src, int64_t bytes)
+{
+    StorageTier& T = *c->tier;
+    TierArray& a = T.arr[(size_t)id];
+    for (int64_t done = 0; done < bytes;) {
+        const ssize_t w = pwrite(a.fd, (const char*)src + done, (size_t)std::min(kChunk, bytes - done), (off_t)(off + done));
+        if (w < 0 && errno == EINTR) continue;
+        if (w < 0) return c->fail(GNN_EHIP, std::string("storage tier: pwrite: ") + std::strerror(errno));
+        done += w;
+    }
+    std::lock_guard<std::mutex> lk(T.mu);
+    T.stats.bytes_written += bytes;
+    T.stats.bypass_bytes += bytes;
     return GNN_OK;
 }
 

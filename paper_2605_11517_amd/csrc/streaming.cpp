@@ -31,6 +31,7 @@
 #include <cstring>
 #include <initializer_list>
 #include <memory>
+#include <utility>
 
 #include "gnn_ctx.h"
 
@@ -110,6 +111,17 @@ struct StreamEngine {
     char* ginbuf(int i) const { return io + (int64_t)(2 + i) * io_bytes; }
     char* ainbuf(int i) const { return io + (int64_t)(4 + i) * io_bytes; }
     char* xinbuf(int i) const { return io + (int64_t)(6 + i) * io_bytes; }   // A^{l-1} blocks of such layers
+    // Storage tier, arrays that are not in host memory: their blocks pass through these pinned
+    // buffers on the way between file and device (allocated on first use)
+    struct Bounce {
+        char* buf = nullptr;
+        hipEvent_t done = nullptr;   // after the copy that uses the buffer
+        bool busy = false, is_write = false;
+        int arr = -1;
+        int64_t off = 0, bytes = 0;
+    };
+    std::vector<Bounce> bounce;
+    size_t next_bounce = 0;
 };
 
 namespace {
@@ -122,6 +134,95 @@ namespace {
     } while (0)
 
 inline int64_t round256(int64_t b) { return (std::max<int64_t>(b, 1) + 255) / 256 * 256; }
+
+// ---- copies between host arrays and the device ---------------------------------------------------
+// A host address is either real (pinned memory: the caller's arrays, or the storage tier's pool)
+// or names a block of an array that the tier keeps on storage only (tier_decode).  The latter go
+// through a pinned buffer: file -> buffer -> device at once, device -> buffer now and buffer ->
+// file once that copy has run (at the latest when the buffer is needed again, when the same array
+// is read, or when the phase ends).
+constexpr int kBounceBuffers = 4;
+
+gnn_status bounce_finish(gnn_ctx* c, StreamEngine::Bounce& b)
+{
+    if (!b.busy) return GNN_OK;
+    GNN_HIP(hipEventSynchronize(b.done));
+    b.busy = false;
+    if (b.is_write) return tier_file_write(c, b.arr, b.off, b.buf, b.bytes);
+    return GNN_OK;
+}
+
+gnn_status bounce_drain(gnn_ctx* c, StreamEngine& E, bool writes_only)
+{
+    // oldest first: blocks reach the file in the order they were produced
+    for (size_t i = 0; i < E.bounce.size(); ++i) {
+        StreamEngine::Bounce& b = E.bounce[(E.next_bounce + i) % E.bounce.size()];
+        if (writes_only && !b.is_write) continue;
+        gnn_status st = bounce_finish(c, b);
+        if (st != GNN_OK) return st;
+    }
+    return GNN_OK;
+}
+
+gnn_status bounce_get(gnn_ctx* c, StreamEngine& E, StreamEngine::Bounce** out)
+{
+    if (E.bounce.empty()) {
+        E.bounce.resize(kBounceBuffers);
+        for (auto& b : E.bounce) {
+            GNN_HIP(hipHostMalloc((void**)&b.buf, (size_t)E.io_bytes, hipHostMallocDefault));
+            GNN_HIP(hipEventCreateWithFlags(&b.done, hipEventDisableTiming));
+        }
+    }
+    StreamEngine::Bounce& b = E.bounce[E.next_bounce];
+    E.next_bounce = (E.next_bounce + 1) % E.bounce.size();
+    gnn_status st = bounce_finish(c, b);      // the buffer used longest ago
+    if (st != GNN_OK) return st;
+    *out = &b;
+    return GNN_OK;
+}
+
+gnn_status copy_h2d(gnn_ctx* c, StreamEngine& E, void* dst_dev, const void* src_host, int64_t bytes, hipStream_t stream)
+{
+    int id;
+    int64_t off;
+    if (!c->tier || !tier_decode(src_host, &id, &off)) {
+        GNN_HIP(hipMemcpyAsync(dst_dev, src_host, (size_t)bytes, hipMemcpyHostToDevice, stream));
+        return GNN_OK;
+    }
+    if (bytes > E.io_bytes) return c->fail(GNN_EINVAL, "storage tier: a block larger than the transfer buffers");
+    gnn_status st = bounce_drain(c, E, true);  // what was produced before must be in the file
+    if (st != GNN_OK) return st;
+    StreamEngine::Bounce* b;
+    if ((st = bounce_get(c, E, &b)) != GNN_OK) return st;
+    if ((st = tier_file_read(c, id, off, b->buf, bytes)) != GNN_OK) return st;
+    GNN_HIP(hipMemcpyAsync(dst_dev, b->buf, (size_t)bytes, hipMemcpyHostToDevice, stream));
+    GNN_HIP(hipEventRecord(b->done, stream));
+    b->busy = true;
+    b->is_write = false;
+    return GNN_OK;
+}
+
+gnn_status copy_d2h(gnn_ctx* c, StreamEngine& E, void* dst_host, const void* src_dev, int64_t bytes, hipStream_t stream)
+{
+    int id;
+    int64_t off;
+    if (!c->tier || !tier_decode(dst_host, &id, &off)) {
+        GNN_HIP(hipMemcpyAsync(dst_host, src_dev, (size_t)bytes, hipMemcpyDeviceToHost, stream));
+        return GNN_OK;
+    }
+    if (bytes > E.io_bytes) return c->fail(GNN_EINVAL, "storage tier: a block larger than the transfer buffers");
+    StreamEngine::Bounce* b;
+    gnn_status st = bounce_get(c, E, &b);
+    if (st != GNN_OK) return st;
+    GNN_HIP(hipMemcpyAsync(b->buf, src_dev, (size_t)bytes, hipMemcpyDeviceToHost, stream));
+    GNN_HIP(hipEventRecord(b->done, stream));
+    b->busy = true;
+    b->is_write = true;
+    b->arr = id;
+    b->off = off;
+    b->bytes = bytes;
+    return GNN_OK;
+}
 
 // ---- pool regions ---------------------------------------------------------------------------
 int64_t pool_alloc(StreamEngine& E, int64_t bytes)
@@ -208,7 +309,9 @@ gnn_status configure(gnn_ctx* c, StreamEngine& E, BlockCache& bc, char* pool, in
     bc.row_bytes = row_bytes;
     bc.host = host;
     bc.host_dev = nullptr;
-    if (host && !identity && direct_gather_enabled()) {
+    int vid;
+    int64_t voff;
+    if (host && !identity && direct_gather_enabled() && !tier_decode(host, &vid, &voff)) {
         // pinned host memory that is mapped for the device can be read (and written) by kernels directly
         hipPointerAttribute_t at;
         if (hipPointerGetAttributes(&at, host) == hipSuccess && at.type == hipMemoryTypeHost && at.devicePointer)
@@ -259,9 +362,10 @@ gnn_status write_back(gnn_ctx* c, StreamEngine& E, BlockCache& bc, int32_t s)
     const HostMeta& M = c->M;
     const int64_t r0 = M.off[(size_t)sl.part], np = M.off[(size_t)sl.part + 1] - r0;
     if (sl.has_released) GNN_HIP(hipStreamWaitEvent(E.d2h, sl.released, 0));
-    if (np > 0)
-        GNN_HIP(hipMemcpyAsync(bc.host + r0 * bc.row_bytes, bc.ptr(s), (size_t)(np * bc.row_bytes),
-                               hipMemcpyDeviceToHost, E.d2h));
+    if (np > 0) {
+        gnn_status cst = copy_d2h(c, E, bc.host + r0 * bc.row_bytes, bc.ptr(s), np * bc.row_bytes, E.d2h);
+        if (cst != GNN_OK) return cst;
+    }
     GNN_HIP(hipEventRecord(sl.flushed, E.d2h));
     sl.has_flushed = true;
     if (!bc.blk_flushed.empty()) {
@@ -357,9 +461,10 @@ gnn_status acquire(gnn_ctx* c, StreamEngine& E, BlockCache& bc, int32_t part, hi
                 GNN_HIP(hipStreamWaitEvent(E.h2d, bc.blk_direct[(size_t)part], 0));    // rows added in host memory
             if (!bc.has_blk_flushed.empty() && bc.has_blk_flushed[(size_t)part])
                 GNN_HIP(hipStreamWaitEvent(E.h2d, bc.blk_flushed[(size_t)part], 0));   // its own last write-back
-            if (np > 0)
-                GNN_HIP(hipMemcpyAsync(bc.ptr(s), bc.host + r0 * bc.row_bytes, (size_t)(np * bc.row_bytes),
-                                       hipMemcpyHostToDevice, E.h2d));
+            if (np > 0) {
+                gnn_status cst = copy_h2d(c, E, bc.ptr(s), bc.host + r0 * bc.row_bytes, np * bc.row_bytes, E.h2d);
+                if (cst != GNN_OK) return cst;
+            }
             GNN_HIP(hipEventRecord(sl.ready, E.h2d));
             sl.has_ready = true;
             sl.waited = false;
@@ -682,6 +787,10 @@ void stream_engine_destroy(gnn_ctx* c)
     }
     if (E->layer_done) (void)hipEventDestroy(E->layer_done);
     if (E->compute_done) (void)hipEventDestroy(E->compute_done);
+    for (auto& b : E->bounce) {
+        if (b.done) (void)hipEventDestroy(b.done);
+        if (b.buf) (void)hipHostFree(b.buf);
+    }
     if (E->pool) (void)hipFree(E->pool);
     if (E->io) (void)hipFree(E->io);
     if (E->xf) (void)hipFree(E->xf);
@@ -733,7 +842,10 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
     auto store_out = [&](int ob, char* dst, int64_t bytes) -> gnn_status {
         GNN_HIP(hipEventRecord(E.out_ready[ob], s));
         GNN_HIP(hipStreamWaitEvent(E.d2h, E.out_ready[ob], 0));
-        if (bytes > 0) GNN_HIP(hipMemcpyAsync(dst, E.outbuf(ob), (size_t)bytes, hipMemcpyDeviceToHost, E.d2h));
+        if (bytes > 0) {
+            gnn_status cst = copy_d2h(c, E, dst, E.outbuf(ob), bytes, E.d2h);
+            if (cst != GNN_OK) return cst;
+        }
         E.d2h_bytes += bytes;
         GNN_HIP(hipEventRecord(E.out_done[ob], E.d2h));
         E.has_out_done[ob] = true;
@@ -754,7 +866,10 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
         GNN_HIP(hipEventRecord(sl.released, s));
         sl.has_released = true;
         GNN_HIP(hipStreamWaitEvent(E.d2h, sl.released, 0));
-        if (bytes > 0) GNN_HIP(hipMemcpyAsync(dst, r->bc.ptr(p), (size_t)bytes, hipMemcpyDeviceToHost, E.d2h));
+        if (bytes > 0) {
+            gnn_status cst = copy_d2h(c, E, dst, r->bc.ptr(p), bytes, E.d2h);
+            if (cst != GNN_OK) return cst;
+        }
         E.d2h_bytes += bytes;
         return GNN_OK;
     };
@@ -774,7 +889,10 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
     // Loads rows of a host array into transfer buffer `dst` on the load stream.
     auto load_in = [&](char* dst, const char* src, int64_t bytes, int ib, bool first) -> gnn_status {
         if (first && E.has_in_released[ib]) GNN_HIP(hipStreamWaitEvent(E.h2d, E.in_released[ib], 0));
-        if (bytes > 0) GNN_HIP(hipMemcpyAsync(dst, src, (size_t)bytes, hipMemcpyHostToDevice, E.h2d));
+        if (bytes > 0) {
+            gnn_status cst = copy_h2d(c, E, dst, src, bytes, E.h2d);
+            if (cst != GNN_OK) return cst;
+        }
         E.h2d_bytes += bytes;
         return GNN_OK;
     };
@@ -843,15 +961,24 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
     // has to move becomes a host synchronisation; arrays may come back at another address, so the
     // host pointers kept by whole arrays in the HBM pool are renewed (those arrays are clean at a
     // phase boundary).
-    auto tier_phase = [&](std::initializer_list<int> need, unsigned overwrite_mask,
+    // need: (array, overwritten whole by the phase) in the order in which they should get room
+    auto tier_phase = [&](std::initializer_list<std::pair<int, bool>> need,
                           std::initializer_list<int> next, std::initializer_list<int> dead) -> gnn_status {
         if (!c->tier) return GNN_OK;
         std::vector<int> nd, nx, dd;
-        for (int id : need) if (id >= 0) nd.push_back(id);
+        unsigned overwrite_mask = 0;
+        for (const auto& nw : need)
+            if (nw.first >= 0) {
+                if (nw.second) overwrite_mask |= 1u << nd.size();
+                nd.push_back(nw.first);
+            }
         for (int id : next) if (id >= 0) nx.push_back(id);
         for (int id : dead) if (id >= 0) dd.push_back(id);
         // only when something has to be read, evicted or moved: otherwise every array stays where
         // it is and the phase is enqueued behind the last one as without the tier
+        // blocks of the last phase still on their way to a file
+        gnn_status b_st = bounce_drain(c, E, false);
+        if (b_st != GNN_OK) return b_st;
         const bool io = tier_needs_io(c, nd.data(), (int)nd.size());
         if (io) {
             GNN_HIP(hipStreamSynchronize(s));
@@ -874,7 +1001,7 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
         const Key keep[2] = {{ARR_ACT, l - 1}, {ARR_ACT, l}};
         // reads A^{l-1}, writes every row of A^l
         if (l == 1 && c->tier) tier_epoch_begin(c);
-        if ((st = tier_phase({act_id(l - 1), act_id(l)}, 2u, {}, {})) != GNN_OK) return st;
+        if ((st = tier_phase({{act_id(l - 1), false}, {act_id(l), true}}, {}, {})) != GNN_OK) return st;
         if (c->transform_first(l)) {
             // Transform-first layer: sweep 1 computes H_p = A_p^{l-1} W for every partition into the
             // whole-graph buffer, sweep 2 gathers and aggregates rows of H.  No partition needs
@@ -977,7 +1104,7 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
         const Key keep[3] = {{ARR_ACT, L}, {ARR_GRAD, L}, {ARR_ACT, L - 1}};
         // reads the logits, writes every row of grad A^L; the backward pass of layer L reads A^{L-1} next
         // (the output layer has no activation to differentiate: the logits are not read again)
-        if ((st = tier_phase({act_id(L), grad_id(L)}, 2u, {act_id(L - 1)}, {act_id(L)})) != GNN_OK) return st;
+        if ((st = tier_phase({{act_id(L), false}, {grad_id(L), true}}, {act_id(L - 1)}, {act_id(L)})) != GNN_OK) return st;
         Resident* logits = find_array(E, keep[0]);
         Resident* gout = nullptr;
         // kept for the backward pass of layer L only if there is free room for it
@@ -1033,9 +1160,11 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
         const int64_t a_blk = round256(a_slot), g_blk = round256(g_slot);      // slots of a block cache
         // reads grad A^l, A^l (hidden layers) and A^{l-1}, writes every row of grad A^{l-1}; the
         // layer below reads A^{l-2} next
-        if ((st = tier_phase({grad_id(l), act_id(l - 1), l < L ? act_id(l) : -1, grad_id(l - 1)},
-                             (l >= 2 ? (l < L ? 8u : 4u) : 0u), {act_id(l - 2)},
-                             {grad_id(l), l < L ? act_id(l) : -1})) != GNN_OK) return st;
+        // (room goes first to the gather source, whose rows are read by many partitions, then to the
+        // gradient being accumulated; grad A^l and A^l are read one own block per partition)
+        if ((st = tier_phase({{act_id(l - 1), false}, {grad_id(l - 1), true}, {grad_id(l), false},
+                              {l < L ? act_id(l) : -1, false}},
+                             {act_id(l - 2)}, {grad_id(l), l < L ? act_id(l) : -1})) != GNN_OK) return st;
         if (c->transform_first(l)) {
             // Transform-first layer: sweep 1 scatter-accumulates S_p^T dY_p into the whole-graph
             // buffer grad H (so no block of grad A^{l-1} is ever cycled through a cache), sweep 2
@@ -1309,6 +1438,7 @@ gnn_status epoch_streaming(gnn_ctx* c, hipStream_t s, float* loss_out)
     GNN_HIP(hipStreamSynchronize(s));
     GNN_HIP(hipStreamSynchronize(E.h2d));
     GNN_HIP(hipStreamSynchronize(E.d2h));
+    if (c->tier && (st = bounce_drain(c, E, false)) != GNN_OK) return st;
     GNN_HIP(hipMemcpy(loss_out, scal, sizeof(float), hipMemcpyDeviceToHost));
     c->loss_done = true;
     c->stream_stats.act_loads = E.loads[0];
