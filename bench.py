@@ -527,7 +527,7 @@ def main():
         sys.exit("bench.py: no GPU visible")
 
     primary = args.workload or "large"
-    others = [x for x in (args.also.split(",") if args.also else ([] if args.workload else ["mid"])) if x]
+    others = [x for x in (args.also.split(",") if args.also else ([] if args.workload else ["mid", "dense"])) if x]
     if primary == "large" and torch.cuda.get_device_properties(0).total_memory < 250 * 2 ** 30:
         sys.exit("bench.py: the large workload needs 250 GB of device memory")
     out = run_workload(primary, args, args.steps, args.warmup, not args.no_cpu_baseline)
