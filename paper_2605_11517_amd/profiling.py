@@ -4,6 +4,10 @@
     python -m paper_2605_11517_amd.profiling pmc    <fetch-dir> <write-dir> <out.md> "<command>"
 
     python -m paper_2605_11517_amd.profiling mfma   <pmc-dir> <out.md> "<command>"
+    python -m paper_2605_11517_amd.profiling counters <pmc-dir> <out.md> "<command>"
+
+``counters`` takes any ``--pmc ... --kernel-trace`` run and lists, per kernel, the number of
+dispatches and the sum of every collected counter over them.
 
 ``mfma`` expects one counter run with ``--pmc SQ_BUSY_CU_CYCLES SQ_VALU_MFMA_BUSY_CYCLES
 --kernel-trace`` and reports, per contraction kernel, the clock the compute units ran at
@@ -152,6 +156,28 @@ def summarize_mfma(src_dir: str, out_path: str, command: str, commit: str = "") 
     open(out_path, "w").write("\n".join(lines) + "\n")
 
 
+def summarize_counters(src_dir: str, out_path: str, command: str, commit: str = "") -> None:
+    path = _one(os.path.join(src_dir, "*counter_collection.csv"))
+    per = collections.OrderedDict()
+    names = []
+    for r in csv.DictReader(open(path)):
+        e = per.setdefault(short_name(r["Kernel_Name"]), collections.OrderedDict())
+        cn = r["Counter_Name"]
+        if cn not in names:
+            names.append(cn)
+        tot, cnt = e.get(cn, (0.0, 0))
+        e[cn] = (tot + float(r["Counter_Value"]), cnt + 1)
+    lines = ["# rocprofv3 --pmc " + " ".join(names), "", "Command:", "", "    " + command, ""]
+    if commit:
+        lines += ["Taken at commit %s." % commit, ""]
+    lines += ["Sums over all dispatches of a kernel.", "",
+              "| kernel | dispatches | " + " | ".join(names) + " |", "|---|---:|" + "---:|" * len(names)]
+    for k, e in per.items():
+        n = max(c for _, c in e.values())
+        lines.append("| %s | %d | " % (k, n) + " | ".join("%.4g" % e.get(cn, (0.0, 0))[0] for cn in names) + " |")
+    open(out_path, "w").write("\n".join(lines) + "\n")
+
+
 def read_taken_at(path: str):
     """The commit a summary says it was taken at (a line 'Taken at commit <hash>'), or None."""
     try:
@@ -180,6 +206,8 @@ if __name__ == "__main__":
         summarize_stats(sys.argv[2], sys.argv[3], sys.argv[4], *sys.argv[5:6])
     elif len(sys.argv) >= 5 and sys.argv[1] == "mfma":
         summarize_mfma(sys.argv[2], sys.argv[3], sys.argv[4], *sys.argv[5:6])
+    elif len(sys.argv) >= 5 and sys.argv[1] == "counters":
+        summarize_counters(sys.argv[2], sys.argv[3], sys.argv[4], *sys.argv[5:6])
     elif len(sys.argv) >= 6 and sys.argv[1] == "pmc":
         summarize_pmc(sys.argv[2], sys.argv[3], sys.argv[4], sys.argv[5], *sys.argv[6:7])
     else:
