@@ -269,6 +269,71 @@ __global__ __launch_bounds__(kBlock) void k_act_bwd_bf16(const float* __restrict
     }
 }
 
+// The same for widths that are multiples of 4 (16-byte aligned rows): a block covers 256 rows x
+// 256 columns, a thread four consecutive columns (16 bytes of g, 8 of act and dy) of every fourth
+// row with four rows in flight; the four row groups are combined through LDS in a fixed order.
+// The grid has one block per (row block, column chunk), so that a partition of 6*10^4 rows still
+// gives every CU several workgroups.
+__global__ __launch_bounds__(kBlock) void k_act_bwd_bf16_vec(const float* __restrict__ g,
+                                                             const uint16_t* __restrict__ act,
+                                                             uint16_t* __restrict__ dy, int64_t rows,
+                                                             int32_t d, float* __restrict__ partial,
+                                                             float scale)
+{
+    __shared__ float4 sm[kBlock];
+    constexpr int CT = 64, RG = kBlock / CT;               // column threads, row groups
+    const int64_t r0 = (int64_t)blockIdx.x * kRowsPerBlockAct;
+    const int64_t r1 = r0 + kRowsPerBlockAct < rows ? r0 + kRowsPerBlockAct : rows;
+    const int rsub = threadIdx.x / CT;
+    const int32_t c = ((int32_t)blockIdx.y * CT + threadIdx.x % CT) * 4;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (c < d) {
+        constexpr int U = 4;
+        for (int64_t r = r0 + rsub; r < r1; r += (int64_t)RG * U) {
+            float4 gv[U];
+            uint2 av[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int64_t rr = r + (int64_t)u * RG;
+                gv[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                av[u] = make_uint2(0x3F803F80u, 0x3F803F80u);             // 1.0 four times
+                if (rr < r1) {
+                    gv[u] = *reinterpret_cast<const float4*>(g + rr * d + c);
+                    if (act) av[u] = *reinterpret_cast<const uint2*>(act + rr * d + c);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int64_t rr = r + (int64_t)u * RG;
+                const uint32_t a4[4] = {av[u].x & 0xFFFFu, av[u].x >> 16, av[u].y & 0xFFFFu, av[u].y >> 16};
+                const float g4[4] = {gv[u].x, gv[u].y, gv[u].z, gv[u].w};
+                float v4[4];
+                uint32_t b4[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    // positive bfloat16: sign bit clear and not zero
+                    const bool pos = (a4[e] & 0x8000u) == 0 && (a4[e] & 0x7FFFu) != 0;
+                    v4[e] = pos ? g4[e] * scale : 0.f;
+                    const uint32_t b = __float_as_uint(v4[e]);
+                    b4[e] = (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;
+                }
+                if (rr < r1)
+                    *reinterpret_cast<uint2*>(dy + rr * d + c) = make_uint2(b4[0] | (b4[1] << 16), b4[2] | (b4[3] << 16));
+                s.x += v4[0]; s.y += v4[1]; s.z += v4[2]; s.w += v4[3];
+            }
+        }
+    }
+    sm[threadIdx.x] = s;
+    __syncthreads();
+    if (rsub == 0 && c < d) {
+        for (int q = 1; q < RG; ++q) {
+            const float4 o = sm[q * CT + threadIdx.x];
+            s.x += o.x; s.y += o.y; s.z += o.z; s.w += o.w;
+        }
+        *reinterpret_cast<float4*>(partial + (int64_t)blockIdx.x * d + c) = s;
+    }
+}
+
 // gb[c] += sum_b partial[b, c]: a block of 1024 threads owns 32 columns; its 32 row groups walk
 // the partial rows 32 apart, eight loads in flight each, and are combined through LDS in a fixed
 // order (a partition of 8*10^5 rows leaves 3*10^3 partial rows: with 8 row groups the walk took
@@ -558,8 +623,15 @@ void launch_act_bwd_bf16(const float* g, const void* act, void* dy, int64_t rows
     if (rows <= 0) return;
     if (!act) scale = 1.f;
     const int64_t blocks = (rows + kRowsPerBlockAct - 1) / kRowsPerBlockAct;
-    hipLaunchKernelGGL(k_act_bwd_bf16, dim3((unsigned)blocks), dim3(kBlock), 0, s, g,
-                       (const uint16_t*)act, (uint16_t*)dy, rows, d, partial, scale);
+    const bool vec = d % 4 == 0 && (reinterpret_cast<uintptr_t>(g) & 15) == 0 &&
+                     (reinterpret_cast<uintptr_t>(partial) & 15) == 0 &&
+                     ((reinterpret_cast<uintptr_t>(act) | reinterpret_cast<uintptr_t>(dy)) & 7) == 0;
+    if (vec)
+        hipLaunchKernelGGL(k_act_bwd_bf16_vec, dim3((unsigned)blocks, (unsigned)((d / 4 + 63) / 64)), dim3(kBlock),
+                           0, s, g, (const uint16_t*)act, (uint16_t*)dy, rows, d, partial, scale);
+    else
+        hipLaunchKernelGGL(k_act_bwd_bf16, dim3((unsigned)blocks), dim3(kBlock), 0, s, g,
+                           (const uint16_t*)act, (uint16_t*)dy, rows, d, partial, scale);
     if (gb)
         hipLaunchKernelGGL(k_colsum_finish, dim3((unsigned)((d + 31) / 32)), dim3(32 * kFinishGroups), 0, s,
                            (const float*)partial, blocks, d, gb);

@@ -43,6 +43,15 @@ __device__ inline uint32_t float_to_bf16(float f)
     return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
 
+// two floats rounded to nearest even and packed (lo | hi << 16): one conversion instruction
+__device__ inline uint32_t pack_bf16(float lo, float hi)
+{
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    typedef float floatx2 __attribute__((ext_vector_type(2)));
+    const floatx2 f = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
+}
+
 // (slow = m or n, fast = k): thread t covers slow = t / 4 + 64 i, k = 8 (t % 4) .. + 7.
 template <int BT, bool VEC>
 __device__ inline void load_kfast(const bf16_t* __restrict__ p, int64_t ld, int64_t slow0,
@@ -471,6 +480,128 @@ __device__ inline void wide_store(const Args& g, floatx16 (&acc)[4][2], char* wl
         }
 }
 
+struct WideFrag {
+    bf16x8 a[4], b[2];
+};
+typedef int v4i32 __attribute__((ext_vector_type(4)));
+// The six fragment reads of one 16-deep step as one asm statement.  The compiler does not see
+// that their results arrive later, so it places no wait of its own; the kernel waits by count
+// (WIDE_WAIT_LDS).  Written as plain loads, a step's reads are waited for right where they are
+// issued (the compiler keeps one set of fragment registers), and every step then costs a wave
+// two LDS round trips on top of its MFMAs.
+// a_addr / b_addr: LDS byte address of this lane's chunk in row block 0 of the A / B tile; the
+// other row blocks are 32 rows (4096 bytes) further each.
+__device__ inline void wide_frags(WideFrag& f, uint32_t a_addr, uint32_t b_addr)
+{
+    v4i32 a0, a1, a2, a3, b0, b1;
+    asm volatile(
+        "ds_read_b128 %0, %6\n\t"
+        "ds_read_b128 %4, %7\n\t"
+        "ds_read_b128 %1, %6 offset:4096\n\t"
+        "ds_read_b128 %5, %7 offset:4096\n\t"
+        "ds_read_b128 %2, %6 offset:8192\n\t"
+        "ds_read_b128 %3, %6 offset:12288"
+        : "=&v"(a0), "=&v"(a1), "=&v"(a2), "=&v"(a3), "=&v"(b0), "=&v"(b1)
+        : "v"(a_addr), "v"(b_addr)
+        : "memory");
+    f.a[0] = __builtin_bit_cast(bf16x8, a0);
+    f.a[1] = __builtin_bit_cast(bf16x8, a1);
+    f.a[2] = __builtin_bit_cast(bf16x8, a2);
+    f.a[3] = __builtin_bit_cast(bf16x8, a3);
+    f.b[0] = __builtin_bit_cast(bf16x8, b0);
+    f.b[1] = __builtin_bit_cast(bf16x8, b1);
+}
+__device__ inline void wide_mfma(floatx16 (&acc)[4][2], const WideFrag& f)
+{
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
+}
+// waits until at most `pending` of this wavefront's LDS reads are outstanding (6: the step just
+// requested; 0: none), and keeps the compiler from moving anything across
+#define WIDE_WAIT_LDS(pending)                                             \
+    do {                                                                   \
+        __builtin_amdgcn_sched_barrier(0);                                 \
+        __builtin_amdgcn_s_waitcnt(0xC07F | ((pending) << 8));             \
+        __builtin_amdgcn_sched_barrier(0);                                 \
+    } while (0)
+
+// The same kernel with the fragment reads of step s + 1 issued before the MFMAs of step s.  The
+// barrier that opens stage t + 1 sits before the last step of stage t: by then a wave has read
+// all of stage t into registers, so after the barrier it issues the loads of stage t + 2 into
+// that buffer, asks for the first fragments of stage t + 1, and only then runs the last step's
+// MFMAs.
+__global__ __launch_bounds__(WTHREADS) void k_gemm_bf16_wide_pipe(const Args g)
+{
+    extern __shared__ __attribute__((aligned(1024))) char wlds[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm = wave >> 2, wn = wave & 3;
+    int64_t mtile;
+    int32_t ntile;
+    if (!tile_of_block(blockIdx.x, (g.m + WBM - 1) / WBM, g.nt_1d, mtile, ntile)) return;
+    const int64_t m0 = mtile * WBM;
+    const int32_t n0 = ntile * WBN;
+    const int nstages = g.kseg[0] / WBK;
+
+    floatx16 acc[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    wide_issue(g.a[0], g.lda[0], m0, g.m, 0, wlds, wave, lane);
+    wide_issue(g.b[0], g.ldb[0], n0, g.n, 0, wlds + WBM * WROWB, wave, lane);
+    if (nstages > 1) {
+        wide_issue(g.a[0], g.lda[0], m0, g.m, WBK, wlds + WSTAGE, wave, lane);
+        wide_issue(g.b[0], g.ldb[0], n0, g.n, WBK, wlds + WSTAGE + WBM * WROWB, wave, lane);
+        __builtin_amdgcn_s_waitcnt(0x0F78);           // vmcnt(8): stage 0 landed, stage 1 may be in flight
+    } else {
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+    }
+    __syncthreads();
+    // this lane's fragment addresses in buffer 0: step ks is chunk 2 ks + half, stored in slot
+    // (2 ks + half) ^ ((x >> 1) & 7) of row x, i.e. 16 * ((half ^ sw) ^ 2 ks) with sw = (xl >> 1) & 7
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)wlds;
+    const int xl = lane & 31, half = lane >> 5;
+    const uint32_t sw16 = (uint32_t)((half ^ ((xl >> 1) & 7)) << 4);
+    const uint32_t a_base = lds0 + (uint32_t)((wm * WTM + xl) * WROWB);
+    const uint32_t b_base = lds0 + (uint32_t)(WBM * WROWB + (wn * WTN + xl) * WROWB);
+    WideFrag f0, f1;
+    wide_frags(f0, a_base + sw16, b_base + sw16);
+    WIDE_WAIT_LDS(0);
+    for (int t = 0; t < nstages; ++t) {
+        const uint32_t cur = (uint32_t)((t & 1) * WSTAGE), nxt = (uint32_t)(((t + 1) & 1) * WSTAGE);
+        wide_frags(f1, a_base + cur + (sw16 ^ 32u), b_base + cur + (sw16 ^ 32u));
+        WIDE_WAIT_LDS(6);
+        wide_mfma(acc, f0);
+        wide_frags(f0, a_base + cur + (sw16 ^ 64u), b_base + cur + (sw16 ^ 64u));
+        WIDE_WAIT_LDS(6);
+        wide_mfma(acc, f1);
+        wide_frags(f1, a_base + cur + (sw16 ^ 96u), b_base + cur + (sw16 ^ 96u));
+        WIDE_WAIT_LDS(6);
+        wide_mfma(acc, f0);
+        WIDE_WAIT_LDS(0);                              // all of stage t is in registers
+        if (t + 1 < nstages) {
+            __builtin_amdgcn_s_waitcnt(0x0F70);       // stage t + 1 landed (this thread's loads)
+            __syncthreads();                           // ... everybody's; nobody reads stage t any more
+            if (t + 2 < nstages) {
+                wide_issue(g.a[0], g.lda[0], m0, g.m, (int64_t)(t + 2) * WBK, wlds + cur, wave, lane);
+                wide_issue(g.b[0], g.ldb[0], n0, g.n, (int64_t)(t + 2) * WBK, wlds + cur + WBM * WROWB, wave, lane);
+            }
+            wide_frags(f0, a_base + nxt + sw16, b_base + nxt + sw16);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        wide_mfma(acc, f1);
+        WIDE_WAIT_LDS(0);                              // f0 is there before the values cross the loop edge
+    }
+    wide_store(g, acc, wlds, m0, n0, wave, lane, wm, wn);
+}
+
 // requires: one K segment, K a multiple of 64, 16-byte aligned rows of A and B
 __global__ __launch_bounds__(WTHREADS) void k_gemm_bf16_wide(const Args g)
 {
@@ -528,104 +659,113 @@ __global__ __launch_bounds__(WTHREADS) void k_gemm_bf16_wide(const Args g)
 }
 
 // ---------------------------------------------------------------------------------------------
-// The same product with a ring of four 32-deep stages instead of two 64-deep ones, and with
-// the fragment reads one step ahead of the MFMAs that use them.
-//
-// What held the two-stage kernel at a third of the matrix pipe: its loop asked for a step's
-// fragments and waited for all of them before the step's MFMAs (the LDS latency was exposed after
-// every four MFMAs), and a stage's loads were in flight for one stage of arithmetic only, less
-// than the latency of a row tile's first fetch from HBM.  Here a stage (256 + 256 rows of 64
-// bytes, 32 KB) is loaded three stages before it is needed... two stages of arithmetic ahead of
-// its first use, three buffers ahead in the ring; a step's fragments (k = 16 of one stage) are
-// requested while the previous step's MFMAs run, across the stage boundary too: the barrier
-// that opens stage t + 1 sits in the middle of stage t.
-//
-// Tile rows are 64 bytes (four 16-byte chunks); chunk c of row x lies in slot c ^ ((x >> 2) & 3),
-// which spreads the sixteen rows of a quarter-wavefront read over all banks.
-constexpr int RBK = 32, RSTAGES = 4;
-constexpr int RROWB = RBK * 2;                         // bytes per tile row
-constexpr int RSTAGE = (WBM + WBN) * RROWB;            // bytes per stage (32 KB)
-constexpr int RLDS = RSTAGES * RSTAGE > 8 * WTM * WCS ? RSTAGES * RSTAGE : 8 * WTM * WCS;
+// The same product on a persistent grid, for bf16 results: one workgroup per CU walks its tiles
+// (tile_of_block order, a grid stride apart) in one continuous sequence of K stages, so that
+//   * the first stage of the next tile is loaded while the last stage of this one is multiplied
+//     (no pipeline fill per tile), and
+//   * a finished tile leaves the accumulators as packed bf16 pairs (64 registers), and each K
+//     stage of the next tile stores one sixteenth of it: 8 rows of the wavefront's columns,
+//     straight from the registers in 64-byte pieces (the stores cost the loop nothing; a turn
+//     through LDS to make them 16 bytes per lane cost 700 cycles a stage in waits).
+// What this is for: a tile's 128 KB of results written in one burst by every CU at the same time
+// (the tiles of a launch run in step) leaves at the chip's write rate, and the store instructions
+// stall at issue meanwhile - a quarter of the tile's time with K = 1024.  Spread over the next
+// tile's stages the same bytes leave while the matrix pipe works.
+constexpr int PLDS = 2 * WSTAGE;
 
-__device__ inline int ring_chunk(int x, int c) { return x * RROWB + ((c ^ ((x >> 2) & 3)) << 4); }
-
-// one operand tile of a stage: 256 rows x 64 bytes, two 1 KB blocks (16 rows each) per wavefront
-__device__ inline void ring_issue(const bf16_t* __restrict__ p, int64_t ld, int64_t row0, int64_t nrows,
-                                  int64_t k0, char* lds_tile, int wave, int lane)
+// Byte offsets of this lane's four 16-byte pieces of a stage tile, from the tile's first row
+// (rows past the end: the last valid row, whose values are never used).
+__device__ inline void persist_offsets(int64_t ld, int64_t row0, int64_t nrows, int wave, int lane, uint32_t (&off)[4])
+{
+    const int64_t last = nrows - 1 - row0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int row = (j * 8 + wave) * 8 + (lane >> 3);
+        const int c = (lane & 7) ^ ((row >> 1) & 7);   // LDS slot lane & 7 of the row holds chunk c
+        const int64_t rl = row < last ? row : last;
+        off[j] = (uint32_t)((rl * ld + c * 8) * 2);
+    }
+}
+// One operand tile of a stage; base: the tile's first row at this stage's k (uniform).
+__device__ inline void persist_issue(const bf16_t* base, const uint32_t (&off)[4], char* lds_tile, int wave)
 {
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int q = j * 8 + wave;
-        const int row = q * 16 + (lane >> 2);
-        const int c = (lane & 3) ^ ((row >> 2) & 3);   // LDS slot lane & 3 of the row holds chunk c
-        int64_t gr = row0 + row;
-        gr = gr < nrows ? gr : nrows - 1;              // rows past the end: valid address, result unused
-        const bf16_t* src = p + gr * ld + k0 + c * 8;
+    for (int j = 0; j < 4; ++j) {
+        const int q = j * 8 + wave;                    // block of 8 rows = 1 KB of LDS
+        const char* src = reinterpret_cast<const char*>(base) + off[j];
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                          (__attribute__((address_space(3))) void*)(lds_tile + q * 1024), 16, 0, 0);
     }
 }
 
-struct RingFrag {
-    bf16x8 a[4], b[2];
+struct ParkedTile {
+    uint32_t v[64];       // (i, j, r even | r odd << 16): index (i * 2 + j) * 8 + r / 2
+    int64_t m0;
+    int32_t n0;
 };
-typedef int v4i32 __attribute__((ext_vector_type(4)));
-// The six fragment reads of one step as one asm statement.  The compiler does not see that
-// their results arrive later, so it places no wait of its own; the kernel waits by count at the
-// points marked below.  (Written as plain loads, the reads of the next step would be waited for
-// together with those of the current one: the compiler's wait before a step's first MFMA covers
-// everything outstanding whenever some path into the block has nothing newer in flight.)
-// a_addr / b_addr: LDS byte address of this lane's chunk in row block 0 of the A / B tile; the
-// other row blocks are 32 rows (2048 bytes) further each.
-__device__ inline void ring_frags(RingFrag& f, uint32_t a_addr, uint32_t b_addr)
-{
-    v4i32 a0, a1, a2, a3, b0, b1;
-    asm volatile(
-        "ds_read_b128 %0, %6\n\t"
-        "ds_read_b128 %1, %6 offset:2048\n\t"
-        "ds_read_b128 %2, %6 offset:4096\n\t"
-        "ds_read_b128 %3, %6 offset:6144\n\t"
-        "ds_read_b128 %4, %7\n\t"
-        "ds_read_b128 %5, %7 offset:2048"
-        : "=&v"(a0), "=&v"(a1), "=&v"(a2), "=&v"(a3), "=&v"(b0), "=&v"(b1)
-        : "v"(a_addr), "v"(b_addr)
-        : "memory");
-    f.a[0] = __builtin_bit_cast(bf16x8, a0);
-    f.a[1] = __builtin_bit_cast(bf16x8, a1);
-    f.a[2] = __builtin_bit_cast(bf16x8, a2);
-    f.a[3] = __builtin_bit_cast(bf16x8, a3);
-    f.b[0] = __builtin_bit_cast(bf16x8, b0);
-    f.b[1] = __builtin_bit_cast(bf16x8, b1);
-}
-__device__ inline void ring_mfma(floatx16 (&acc)[4][2], const RingFrag& f)
-{
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
-}
-// waits until at most `pending` of this wavefront's LDS reads are outstanding (6: the step just
-// requested; 0: none), and keeps the compiler from moving anything across
-#define RING_WAIT_LDS(pending)                                             \
-    do {                                                                   \
-        __builtin_amdgcn_sched_barrier(0);                                 \
-        __builtin_amdgcn_s_waitcnt(0xC07F | ((pending) << 8));             \
-        __builtin_amdgcn_sched_barrier(0);                                 \
-    } while (0)
 
-// requires: one K segment, K a multiple of 32, 16-byte aligned rows of A and B
-__global__ __launch_bounds__(WTHREADS) void k_gemm_bf16_ring(const Args g)
+// Stores chunk `chunk` (0..15) of the parked tile: rows 8 chunk .. + 7 of the wavefront's 128, its
+// 64 columns, straight from the MFMA layout: lane (half, xl) holds column 32 j + xl of rows
+// 4 half + 2 h and + 1, so a store instruction writes 64 contiguous bytes of two rows, and the two
+// column blocks complete each 128-byte line right after one another.  Only the choice of the four
+// registers depends on the chunk at compile time.
+__device__ inline void persist_store(const Args& g, const ParkedTile& pk, int chunk, int lane, int wm, int wn)
+{
+    uint32_t pr[2][2];                                 // [j][h]
+    switch (chunk) {
+#define GNN_CHUNK(C)                                                       \
+    case C:                                                                \
+        pr[0][0] = pk.v[((C) / 4 * 2 + 0) * 8 + 2 * ((C) % 4)];            \
+        pr[0][1] = pk.v[((C) / 4 * 2 + 0) * 8 + 2 * ((C) % 4) + 1];        \
+        pr[1][0] = pk.v[((C) / 4 * 2 + 1) * 8 + 2 * ((C) % 4)];            \
+        pr[1][1] = pk.v[((C) / 4 * 2 + 1) * 8 + 2 * ((C) % 4) + 1];        \
+        break;
+        GNN_CHUNK(0) GNN_CHUNK(1) GNN_CHUNK(2) GNN_CHUNK(3) GNN_CHUNK(4) GNN_CHUNK(5) GNN_CHUNK(6) GNN_CHUNK(7)
+        GNN_CHUNK(8) GNN_CHUNK(9) GNN_CHUNK(10) GNN_CHUNK(11) GNN_CHUNK(12) GNN_CHUNK(13) GNN_CHUNK(14) GNN_CHUNK(15)
+#undef GNN_CHUNK
+        default: return;
+    }
+    const int half = lane >> 5, xl = lane & 31;
+    const int64_t row0 = pk.m0 + wm * WTM + 8 * chunk + 4 * half;
+    const int32_t col0 = pk.n0 + wn * WTN + xl;
+    bf16_t* cp = static_cast<bf16_t*>(g.c) + row0 * g.ldc + col0;
+    const bool interior = pk.m0 + WBM <= g.m && pk.n0 + WBN <= g.n;
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            if (!interior && col0 + 32 * j >= g.n) continue;
+            if (interior || row0 + 2 * h < g.m) cp[(2 * h) * g.ldc + 32 * j] = (bf16_t)(pr[j][h] & 0xFFFFu);
+            if (interior || row0 + 2 * h + 1 < g.m) cp[(2 * h + 1) * g.ldc + 32 * j] = (bf16_t)(pr[j][h] >> 16);
+        }
+}
+
+// requires: one K segment, K a multiple of 64, 16-byte aligned rows of A and B, bf16 result
+// without accumulation; total = padded number of linear tile indices
+__global__ __launch_bounds__(WTHREADS) void k_gemm_bf16_persist(const Args g, const int32_t total)
 {
     extern __shared__ __attribute__((aligned(1024))) char wlds[];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: kept in scalar registers
     const int wm = wave >> 2, wn = wave & 3;
-    int64_t mtile;
-    int32_t ntile;
-    if (!tile_of_block(blockIdx.x, (g.m + WBM - 1) / WBM, g.nt_1d, mtile, ntile)) return;
-    const int64_t m0 = mtile * WBM;
-    const int32_t n0 = ntile * WBN;
-    const int nst = g.kseg[0] / RBK;
+    const int32_t mt = (int32_t)((g.m + WBM - 1) / WBM);
+    const int nstages = g.kseg[0] / WBK;
+
+    // the tile of linear index `from`, or of the next index a grid stride further that owns one
+    // (padding indices own none); same order as tile_of_block
+    auto next_tile = [&](int32_t from, int32_t& mtile, int32_t& ntile) {
+        for (; from < total; from += (int32_t)gridDim.x) {
+            const int32_t slot = from >> 3;
+            ntile = slot % g.nt_1d;
+            mtile = slot / g.nt_1d * 8 + (from & 7);
+            if (mtile < mt) break;
+        }
+        return from;
+    };
+    int32_t mtile = 0, mtile_n = 0;
+    int32_t ntile = 0, ntile_n = 0;
+    int32_t idx = next_tile((int32_t)blockIdx.x, mtile, ntile);
+    if (idx >= total) return;
 
     floatx16 acc[4][2];
 #pragma unroll
@@ -634,59 +774,96 @@ __global__ __launch_bounds__(WTHREADS) void k_gemm_bf16_ring(const Args g)
         for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-    auto issue = [&](int st) {
-        char* buf = wlds + (st % RSTAGES) * RSTAGE;
-        ring_issue(g.a[0], g.lda[0], m0, g.m, (int64_t)st * RBK, buf, wave, lane);
-        ring_issue(g.b[0], g.ldb[0], n0, g.n, (int64_t)st * RBK, buf + WBM * RROWB, wave, lane);
-    };
-    // every wavefront issues four loads per stage; stages complete in the order they were issued
-    const int ahead = nst < RSTAGES - 1 ? nst : RSTAGES - 1;
-    for (int st = 0; st < ahead; ++st) issue(st);
-    if (ahead >= 3) __builtin_amdgcn_s_waitcnt(0x0F78);        // vmcnt(8): stage 0 has landed
-    else if (ahead == 2) __builtin_amdgcn_s_waitcnt(0x0F74);   // vmcnt(4)
-    else __builtin_amdgcn_s_waitcnt(0x0F70);                   // vmcnt(0)
-    __syncthreads();
-    // this lane's fragment addresses inside a stage, for the two 16-deep steps of a stage
-    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)wlds;
-    const int xl = lane & 31, half = lane >> 5;
-    uint32_t a_off[2], b_off[2];
+    ParkedTile pk;
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-        a_off[ks] = lds0 + (uint32_t)ring_chunk(wm * WTM + xl, 2 * ks + half);
-        b_off[ks] = lds0 + (uint32_t)(WBM * RROWB + ring_chunk(wn * WTN + xl, 2 * ks + half));
+    for (int q = 0; q < 64; ++q) pk.v[q] = 0u;
+    pk.m0 = 0;
+    pk.n0 = 0;
+    bool parked = false;
+
+    int buf = 0;
+    uint32_t offa[4], offb[4];
+    persist_offsets(g.lda[0], (int64_t)mtile * WBM, g.m, wave, lane, offa);
+    persist_offsets(g.ldb[0], (int64_t)ntile * WBN, g.n, wave, lane, offb);
+    persist_issue(g.a[0] + (int64_t)mtile * WBM * g.lda[0], offa, wlds, wave);
+    persist_issue(g.b[0] + (int64_t)ntile * WBN * g.ldb[0], offb, wlds + WBM * WROWB, wave);
+    const int xl = lane & 31, half = lane >> 5;
+    while (true) {
+        const int32_t idx_n = next_tile(idx + (int32_t)gridDim.x, mtile_n, ntile_n);
+        const bool has_next = idx_n < total;
+        const int64_t m0 = (int64_t)mtile * WBM;
+        const int32_t n0 = ntile * WBN;
+        int chunk = 0, due = 0;                        // 16 chunks spread evenly over the stages
+        for (int t = 0; t < nstages; ++t) {
+            __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0): this thread's loads of the stage landed
+            __syncthreads();                           // everybody's did; the other buffer is no longer read
+            char* nxt = wlds + (buf ^ 1) * WSTAGE;
+            if (t + 1 < nstages) {
+                persist_issue(g.a[0] + m0 * g.lda[0] + (int64_t)(t + 1) * WBK, offa, nxt, wave);
+                persist_issue(g.b[0] + (int64_t)n0 * g.ldb[0] + (int64_t)(t + 1) * WBK, offb, nxt + WBM * WROWB, wave);
+            } else if (has_next) {
+                // (the tile numbers pass through an empty asm so that none of this is computed,
+                // and kept in registers, before the loop)
+                int32_t mn = mtile_n, nn = ntile_n;
+                asm volatile("" : "+s"(mn), "+s"(nn));
+                persist_offsets(g.lda[0], (int64_t)mn * WBM, g.m, wave, lane, offa);
+                persist_offsets(g.ldb[0], (int64_t)nn * WBN, g.n, wave, lane, offb);
+                persist_issue(g.a[0] + (int64_t)mn * WBM * g.lda[0], offa, nxt, wave);
+                persist_issue(g.b[0] + (int64_t)nn * WBN * g.ldb[0], offb, nxt + WBM * WROWB, wave);
+            }
+            const char* As = wlds + buf * WSTAGE;
+            const char* Bs = As + WBM * WROWB;
+#pragma unroll
+            for (int ks = 0; ks < WBK / 16; ++ks) {
+                bf16x8 av[4], bv[2];
+                const int c = 2 * ks + half;
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    av[i] = *reinterpret_cast<const bf16x8*>(As + wide_chunk(wm * WTM + 32 * i + xl, c));
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    bv[j] = *reinterpret_cast<const bf16x8*>(Bs + wide_chunk(wn * WTN + 32 * j + xl, c));
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bv[j], acc[i][j], 0, 0, 0);
+                // one sixteenth of the parked tile per stage (more when K < 1024), after a
+                // step's MFMAs are issued; the two wavefronts of a SIMD (w and w + 4: the two
+                // values of wm) at different steps
+                if (ks == (wm == 1 ? 2 : 0) && parked)
+                    for (due += 16; due >= nstages; due -= nstages) persist_store(g, pk, chunk++, lane, wm, wn);
+            }
+            buf ^= 1;
+        }
+        // the tile is complete: + bias, max(., 0), round, park; the accumulators start over
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int32_t col = n0 + wn * WTN + 32 * j + (lane & 31);
+            const float bvl = (g.bias && col < g.n) ? g.bias[col] : 0.f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; r += 2) {
+                    float v0 = acc[i][j][r] + bvl, v1 = acc[i][j][r + 1] + bvl;
+                    if (g.relu) {
+                        v0 = v0 > 0.f ? v0 : 0.f;
+                        v1 = v1 > 0.f ? v1 : 0.f;
+                    }
+                    pk.v[(i * 2 + j) * 8 + r / 2] = pack_bf16(v0, v1);
+                    acc[i][j][r] = 0.f;
+                    acc[i][j][r + 1] = 0.f;
+                }
+        }
+        pk.m0 = m0;
+        pk.n0 = n0;
+        parked = true;
+        if (!has_next) break;
+        idx = idx_n;
+        mtile = mtile_n;
+        ntile = ntile_n;
     }
-    RingFrag f0, f1;
-    ring_frags(f0, a_off[0], b_off[0]);
-    RING_WAIT_LDS(0);
-    // (the last stage is peeled off: the loop body has no branch around its LDS reads)
-    for (int t = 0; t + 1 < nst; ++t) {
-        const uint32_t cur = (uint32_t)((t % RSTAGES) * RSTAGE);
-        const uint32_t nxt = (uint32_t)(((t + 1) % RSTAGES) * RSTAGE);
-        ring_frags(f1, a_off[1] + cur, b_off[1] + cur);
-        RING_WAIT_LDS(6);             // f0 is there (requested a step ago); f1 stays in flight
-        ring_mfma(acc, f0);
-        RING_WAIT_LDS(0);             // f1 is there
-        // stage t + 1 must have landed; of the stages issued so far only t + 2 may be pending
-        if (t + 2 < nst) __builtin_amdgcn_s_waitcnt(0x0F74);
-        else __builtin_amdgcn_s_waitcnt(0x0F70);
-        __syncthreads();              // ... for every wavefront; and nobody reads stage t - 1 any more
-        if (t + RSTAGES - 1 < nst) issue(t + RSTAGES - 1);      // into the buffer stage t - 1 was in
-        ring_frags(f0, a_off[0] + nxt, b_off[0] + nxt);
-        __builtin_amdgcn_sched_barrier(0);
-        ring_mfma(acc, f1);
-        RING_WAIT_LDS(0);             // f0 is there before the values cross the loop edge
-    }
-    if (nst > 0) {
-        const uint32_t cur = (uint32_t)(((nst - 1) % RSTAGES) * RSTAGE);
-        ring_frags(f1, a_off[1] + cur, b_off[1] + cur);
-        RING_WAIT_LDS(6);
-        ring_mfma(acc, f0);
-        RING_WAIT_LDS(0);
-        ring_mfma(acc, f1);
-    }
-    __syncthreads();                  // the store below reuses the ring as staging space
-    wide_store(g, acc, wlds, m0, n0, wave, lane, wm, wn);
+    for (int ch = 0; ch < 16; ++ch) persist_store(g, pk, ch, lane, wm, wn);
 }
 
 // Whether the wide kernel can take this product (both operands k-contiguous is the caller's business).
@@ -707,26 +884,44 @@ bool launch_wide(const Args& g, hipStream_t s)
 {
     static const bool attr_ok = hipFuncSetAttribute((const void*)k_gemm_bf16_wide,
                                                     hipFuncAttributeMaxDynamicSharedMemorySize, WLDS) == hipSuccess;
-    static const bool ring_ok = hipFuncSetAttribute((const void*)k_gemm_bf16_ring,
-                                                    hipFuncAttributeMaxDynamicSharedMemorySize, RLDS) == hipSuccess;
-    static const bool ring = [] {
-        const char* e = getenv("GNNMI_GEMM_RING");
-        return e && e[0] == '1';
+    static const bool persist_ok = hipFuncSetAttribute((const void*)k_gemm_bf16_persist,
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, PLDS) == hipSuccess;
+    static const bool persist = [] {
+        const char* e = getenv("GNNMI_GEMM_PERSIST");
+        return !(e && e[0] == '0');
+    }();
+    // one workgroup fits a CU (LDS), and the grid is one workgroup per CU
+    static const int cus = [] {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8)
+            return 0;
+        return n / 8 * 8;
     }();
     const int64_t mt = (g.m + WBM - 1) / WBM;
     const int32_t nt = (g.n + WBN - 1) / WBN;
     Args ga = g;
     ga.nt_1d = nt;
-    if (ring && ring_ok) {
-        hipLaunchKernelGGL(k_gemm_bf16_ring, dim3((unsigned)((mt + 7) / 8 * 8 * nt)), dim3(WTHREADS), RLDS, s, ga);
+    const int64_t total = (mt + 7) / 8 * 8 * nt;
+    if (persist && persist_ok && cus > 0 && g.out_bf16 && !g.accumulate && total < (1 << 30)) {
+        const int64_t grid = total < cus ? total : cus;
+        hipLaunchKernelGGL(k_gemm_bf16_persist, dim3((unsigned)grid), dim3(WTHREADS), PLDS, s, ga, (int32_t)total);
         return true;
     }
     if (!attr_ok) return false;
-    hipLaunchKernelGGL(k_gemm_bf16_wide, dim3((unsigned)((mt + 7) / 8 * 8 * nt)), dim3(WTHREADS), WLDS, s, ga);
+    static const bool pipe_ok = hipFuncSetAttribute((const void*)k_gemm_bf16_wide_pipe,
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, WLDS) == hipSuccess;
+    static const bool pipe = [] {
+        const char* e = getenv("GNNMI_GEMM_PIPE");
+        return e && e[0] == '1';
+    }();
+    if (pipe && pipe_ok)
+        hipLaunchKernelGGL(k_gemm_bf16_wide_pipe, dim3((unsigned)total), dim3(WTHREADS), WLDS, s, ga);
+    else
+        hipLaunchKernelGGL(k_gemm_bf16_wide, dim3((unsigned)total), dim3(WTHREADS), WLDS, s, ga);
     return true;
 }
 
-// dst [N x K] = src [K x N]^T, 32 x 32 tiles through LDS
 __global__ __launch_bounds__(256) void k_transpose_bf16(const bf16_t* __restrict__ src, int64_t ld, int32_t k,
                                                         int32_t n, bf16_t* __restrict__ dst)
 {

@@ -478,6 +478,10 @@ BF16_CASES = [
     # 5000 rows per partition: the weight gradient's reduction over rows takes the 256 x 256 tile
     # kernel for 78 whole stages of 64 rows and the narrow kernel for the last 8 rows
     ("gcn", (256, 264, 16), 10000, 60000, True, 2, "random"),
+    # 60,000 rows per partition: 235 row tiles x 2 column tiles are more 256 x 256 tiles than the
+    # chip has CUs, so the persistent kernel's workgroups walk several tiles each (padding indices
+    # in between, a 96-row tail, a 64-column tail), with 1, 5 and 8 K stages per tile
+    ("gcn", (64, 320, 512, 16), 120000, 500000, True, 2, "random"),
 ]
 
 
