@@ -913,7 +913,7 @@ bool launch_wide(const Args& g, hipStream_t s)
                                                     hipFuncAttributeMaxDynamicSharedMemorySize, WLDS) == hipSuccess;
     static const bool pipe = [] {
         const char* e = getenv("GNNMI_GEMM_PIPE");
-        return e && e[0] == '1';
+        return !(e && e[0] == '0');
     }();
     if (pipe && pipe_ok)
         hipLaunchKernelGGL(k_gemm_bf16_wide_pipe, dim3((unsigned)total), dim3(WTHREADS), WLDS, s, ga);
