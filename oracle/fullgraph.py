@@ -230,11 +230,16 @@ def adam_step(params, grads, m, v, t, lr, beta1=0.9, beta2=0.999, eps=1e-8, weig
 
 def train(model, rowptr, colidx, dims, X, weights, labels, mask, epochs, optimizer="adam",
           lr=0.01, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0, dropout=0.0, seed=0,
-          first_epoch=0, relu_on=None):
+          first_epoch=0, relu_on=None, weight_round=None):
     """``epochs`` training epochs: forward with dropout on the hidden activations, loss,
     backward, one optimizer step.  Returns the losses, the final weights (same layout as
     ``weights``) and the last epoch's results.  ``relu_on``: optional callable
-    ``(epoch, Forward) -> list`` giving activation decisions for the backward pass."""
+    ``(epoch, Forward) -> list`` giving activation decisions for the backward pass.
+    ``weight_round``: optional callable applied to the matrices ``W`` and ``Ws`` (not the
+    biases) before every forward pass, for weights kept in a narrower storage type: the epoch
+    sees the rounded matrices, the optimizer steps the unrounded ones (weight decay included),
+    and those are what is returned.  The paper trains in one precision; this is the customary
+    master-copy arrangement."""
     L = len(dims) - 1
     n = len(rowptr) - 1
     sage = model == "sage"
@@ -249,7 +254,11 @@ def train(model, rowptr, colidx, dims, X, weights, labels, mask, epochs, optimiz
         drop = None
         if dropout > 0:
             drop = [dropout_multipliers(n, dims[l + 1], dropout, seed, ep, l + 1) for l in range(L - 1)]
-        f = forward(model, rowptr, colidx, dims, X, cur, drop=drop)
+        seen = cur
+        if weight_round is not None:
+            seen = [{"W": _f64(weight_round(w["W"])), "Ws": _f64(weight_round(w["Ws"])) if sage else None,
+                     "b": w["b"]} for w in cur]
+        f = forward(model, rowptr, colidx, dims, X, seen, drop=drop)
         r = backward(f, labels, mask, relu_on=relu_on(ep, f) if relu_on else None)
         last = dict(r, act=f.act)
         losses.append(r["loss"])

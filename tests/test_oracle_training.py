@@ -147,3 +147,51 @@ def test_training_loop_chains_epochs_and_lowers_the_loss():
     drop1 = [og.dropout_multipliers(n, dims[l + 1], 0.3, 5, 1, l + 1) for l in range(2)]
     r1 = og.epoch("sage", rowptr, colidx, dims, X, w1, y, m, drop=drop1)
     assert r1["loss"] == losses[1]
+
+
+def test_training_with_rounded_weights_steps_the_unrounded_copies():
+    """``weight_round``: the epoch sees the rounded matrices, the optimizer steps the unrounded
+    ones (weight decay on the unrounded value too), biases are never rounded."""
+    n, dims = 50, (6, 10, 4)
+    rowptr, colidx = small_graph(n, 200, seed=8, symmetric=True, self_loops=False)
+    rng = np.random.default_rng(3)
+    X = rng.standard_normal((n, dims[0]))
+    y = rng.integers(0, dims[-1], n).astype(np.int32)
+    m = (rng.random(n) < 0.7).astype(np.uint8)
+    w = random_weights(dims, 4, sage=True)
+    coarse = lambda a: np.round(np.asarray(a, dtype=np.float64) * 8.0) / 8.0     # a visibly coarse grid
+    # the identity changes nothing
+    a = og.train("sage", rowptr, colidx, dims, X, w, y, m, epochs=2, lr=0.05, weight_decay=0.1)
+    b = og.train("sage", rowptr, colidx, dims, X, w, y, m, epochs=2, lr=0.05, weight_decay=0.1,
+                 weight_round=lambda t: t)
+    assert a[0] == b[0]
+    for l in range(2):
+        for key in ("W", "Ws", "b"):
+            assert np.array_equal(a[1][l][key], b[1][l][key])
+    # two epochs by hand
+    for opt in ("adam", "sgd"):
+        losses, final, _ = og.train("sage", rowptr, colidx, dims, X, w, y, m, epochs=2, optimizer=opt,
+                                    lr=0.05, weight_decay=0.1, weight_round=coarse)
+        rounded = lambda ws: [{"W": coarse(t["W"]), "Ws": coarse(t["Ws"]), "b": t["b"]} for t in ws]
+        r0 = og.epoch("sage", rowptr, colidx, dims, X, rounded(w), y, m)
+        assert r0["loss"] == losses[0]
+        assert r0["loss"] != og.epoch("sage", rowptr, colidx, dims, X, w, y, m)["loss"]
+        flat = [np.asarray(t, dtype=np.float64) for l in range(2) for t in (w[l]["W"], w[l]["Ws"], w[l]["b"])]
+        grads = [t for l in range(2) for t in (r0["gW"][l], r0["gWs"][l], r0["gb"][l])]
+        if opt == "adam":
+            new, m1, v1 = og.adam_step(flat, grads, [np.zeros_like(t) for t in flat],
+                                       [np.zeros_like(t) for t in flat], 1, 0.05, weight_decay=0.1)
+        else:
+            new = og.sgd_step(flat, grads, 0.05, 0.1)
+        w1 = [{"W": new[3 * l], "Ws": new[3 * l + 1], "b": new[3 * l + 2]} for l in range(2)]
+        assert not np.array_equal(w1[0]["W"], coarse(w1[0]["W"]))      # the copies leave the grid
+        r1 = og.epoch("sage", rowptr, colidx, dims, X, rounded(w1), y, m)
+        assert r1["loss"] == losses[1]
+        grads1 = [t for l in range(2) for t in (r1["gW"][l], r1["gWs"][l], r1["gb"][l])]
+        if opt == "adam":
+            new2, _, _ = og.adam_step(new, grads1, m1, v1, 2, 0.05, weight_decay=0.1)
+        else:
+            new2 = og.sgd_step(new, grads1, 0.05, 0.1)
+        for l in range(2):
+            for j, key in enumerate(("W", "Ws", "b")):
+                assert np.array_equal(final[l][key], new2[3 * l + j]), (opt, l, key)
