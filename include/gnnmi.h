@@ -382,10 +382,20 @@ typedef struct {
  * owned.  Not needed for GNN_OPT_SGD. */
 gnn_status gnn_bind_optimizer(gnn_ctx *ctx, void *const *m, void *const *v);
 
-/* The bound weight buffers are updated in place: weights <- one optimizer step from grad_w
- * (as left by the last epoch); `step` is the
- * 1-based step number (Adam's bias correction).  fp32 weights only: GNN_EUNSUPPORTED for
- * GNN_BF16.  GNN_ESTATE when nothing is bound (or, for Adam, no moments). */
+/* GNN_BF16 only (datasets table: the paper trains in one precision and says nothing of mixed
+ * storage; this is the usual arrangement): fp32 master copies of the weight matrices W and W_s
+ * (device, caller owned, laid out like `weights` in gnn_bind: 3 L entries, the bias entries
+ * are ignored, null where the matrix does not exist).  The caller fills them with the values
+ * whose bfloat16 rounding it bound as `weights`.  GNN_EUNSUPPORTED for GNN_F32, GNN_EINVAL for
+ * a missing or misaligned (4 bytes) copy. */
+gnn_status gnn_bind_master_weights(gnn_ctx *ctx, void *const *master);
+
+/* One optimizer step from grad_w (as left by the last epoch); `step` is the 1-based step
+ * number (Adam's bias correction).  GNN_F32: the bound weight buffers are updated in place.
+ * GNN_BF16: the step is taken in fp32 on the master copies (weight decay uses the master
+ * value), and each bound matrix receives the round-to-nearest-even bfloat16 of its updated
+ * master; biases are fp32 and updated in place.  GNN_ESTATE when nothing is bound, for Adam
+ * without moments, for GNN_BF16 without master copies. */
 gnn_status gnn_optimizer_step(gnn_ctx *ctx, const gnn_optimizer *opt, int64_t step, void *stream);
 
 /* `epochs` times: gnn_set_dropout(p, seed, first_epoch + e), gnn_epoch, gnn_optimizer_step

@@ -108,6 +108,7 @@ def load_library():
         "gnn_layer_transform_bwd": [vp, i32, i32, vp],
         "gnn_set_dropout": [vp, C.c_float, u64, i64],
         "gnn_bind_optimizer": [vp, P(vp), P(vp)],
+        "gnn_bind_master_weights": [vp, P(vp)],
         "gnn_optimizer_step": [vp, P(Optimizer), i64, vp],
         "gnn_train": [vp, P(Optimizer), i32, i64, C.c_float, u64, vp, P(C.c_float)],
         "gnn_set_profiling": [vp, i32],
@@ -311,6 +312,12 @@ class Context:
             return a
         self._check(self.lib.gnn_bind_optimizer(self.h, arr(m), arr(v)))
 
+    def bind_master_weights(self, master):
+        a = (C.c_void_p * max(1, len(master)))()
+        for i, p in enumerate(master):
+            a[i] = p
+        self._check(self.lib.gnn_bind_master_weights(self.h, a))
+
     def optimizer_step(self, opt, step, stream):
         self._check(self.lib.gnn_optimizer_step(self.h, C.byref(opt), int(step), stream))
 
@@ -425,7 +432,7 @@ class Session:
                                     **big))                                  # logits stay fp32
             self.gact.append(t.zeros((self.n, dims[l + 1]), dtype=t.float32, **big))
             say("buffers of layer %d allocated" % (l + 1))
-        self.w, self.gw = [], []
+        self.w, self.gw, self.w32 = [], [], []      # w32: fp32 originals of bfloat16 matrices
         for l in range(self.L):
             for key in ("W", "Ws", "b"):
                 a = weights[l].get(key)
@@ -436,6 +443,7 @@ class Session:
                     and (key != "b" or has_bias)
                 if use:
                     wt = t.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(self.dev)
+                    self.w32.append(wt if key != "b" and self.bf16 else None)
                     if key != "b":
                         wt = self._store(wt)
                     self.w.append(wt)
@@ -443,6 +451,7 @@ class Session:
                 else:
                     self.w.append(None)
                     self.gw.append(None)
+                    self.w32.append(None)
         sb, wb = self.ctx.workspace_bytes()
         self.staging = t.empty(sb, dtype=t.uint8, device=self.dev)
         self.scratch = t.empty(wb, dtype=t.uint8, device=self.dev)
@@ -553,8 +562,28 @@ class Session:
                           for w in self.w]
             ptr = lambda x: x.data_ptr() if x is not None else None
             self.ctx.bind_optimizer([ptr(x) for x in self.opt_m], [ptr(x) for x in self.opt_v])
+        self.bind_master_weights()
         opt = make_optimizer(optimizer, lr, beta1, beta2, eps, weight_decay)
         return self.ctx.train(opt, epochs, first_epoch, dropout, seed, self.stream)
+
+    def bind_master_weights(self):
+        """bfloat16 storage: hands the fp32 originals of the weight matrices to the library as the
+        copies the optimizer updates (once)."""
+        if self.bf16 and not getattr(self, "_masters_bound", False):
+            self.ctx.bind_master_weights([x.data_ptr() if x is not None else None for x in self.w32])
+            self._masters_bound = True
+
+    def master_weights(self):
+        """The fp32 master copies (bfloat16 storage) in the layout of ``weights()``; biases are
+        the bound fp32 ones."""
+        out = []
+        for l in range(self.L):
+            W, Ws = self.w32[3 * l], self.w32[3 * l + 1]
+            b = self.w[3 * l + 2]
+            out.append({"W": W.cpu().numpy() if W is not None else None,
+                        "Ws": Ws.cpu().numpy() if Ws is not None else None,
+                        "b": b.float().cpu().numpy() if b is not None else None})
+        return out
 
     def weights(self):
         """The bound weights as a list of dicts of numpy arrays (the layout of ``weights``)."""

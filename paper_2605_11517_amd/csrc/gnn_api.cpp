@@ -1703,11 +1703,31 @@ gnn_status gnn_bind_optimizer(gnn_ctx* c, void* const* m, void* const* v)
     return GNN_OK;
 }
 
+gnn_status gnn_bind_master_weights(gnn_ctx* c, void* const* master)
+{
+    if (!c || !master) return GNN_EINVAL;
+    if (!c->bf16())
+        return c->fail(GNN_EUNSUPPORTED, "fp32 weights are updated in place: master copies belong to GNN_BF16");
+    const int32_t L = c->L;
+    std::vector<float*> mw((size_t)3 * L, nullptr);
+    for (int32_t l = 0; l < L; ++l)
+        for (int j = 0; j < 2; ++j) {
+            const bool needed = j == 0 || c->model != GNN_GCN;
+            if (!needed) continue;
+            if (!master[3 * l + j] || (reinterpret_cast<uintptr_t>(master[3 * l + j]) & 3) != 0)
+                return c->fail(GNN_EINVAL, "gnn_bind_master_weights: a master copy of an existing matrix is null or unaligned");
+            mw[(size_t)(3 * l + j)] = (float*)master[3 * l + j];
+        }
+    c->master.swap(mw);
+    return GNN_OK;
+}
+
 gnn_status gnn_optimizer_step(gnn_ctx* c, const gnn_optimizer* opt, int64_t step, void* stream)
 {
     if (!c || !opt) return GNN_EINVAL;
     if (!c->bound) return c->fail(GNN_ESTATE, "gnn_optimizer_step before gnn_bind");
-    if (c->bf16()) return c->fail(GNN_EUNSUPPORTED, "the optimizer step takes fp32 weights");
+    if (c->bf16() && c->master.empty())
+        return c->fail(GNN_ESTATE, "bfloat16 weights are stepped through fp32 master copies: call gnn_bind_master_weights");
     if (opt->kind != GNN_OPT_SGD && opt->kind != GNN_OPT_ADAM) return c->fail(GNN_EINVAL, "unknown optimizer");
     if (step < 1) return c->fail(GNN_EINVAL, "step numbers start at 1");
     if (opt->kind == GNN_OPT_ADAM && c->opt_m.empty())
@@ -1723,14 +1743,21 @@ gnn_status gnn_optimizer_step(gnn_ctx* c, const gnn_optimizer* opt, int64_t step
             if (!w || !g) continue;
             if (j == 1 && c->model == GNN_GCN) continue;
             if (j == 2 && !c->has_bias) continue;
+            // bfloat16 storage: the step is taken on the fp32 master copy of a matrix, and the
+            // bound matrix receives its rounding (biases are fp32 and stepped in place)
+            void* w16 = nullptr;
+            if (c->bf16() && j < 2) {
+                w16 = w;
+                w = c->master[(size_t)(3 * l + j)];
+            }
             int64_t cnt = j == 2 ? (int64_t)c->dims[(size_t)l + 1]
                                  : (int64_t)c->dims[(size_t)l] * c->dims[(size_t)l + 1];
             if (j == 1 && c->model == GNN_GAT) cnt = (int64_t)2 * c->dims[(size_t)l + 1];
             if (opt->kind == GNN_OPT_ADAM)
                 launch_adam(w, g, c->opt_m[(size_t)(3 * l + j)], c->opt_v[(size_t)(3 * l + j)], cnt, opt->lr,
-                            opt->beta1, opt->beta2, opt->eps, opt->weight_decay, corr1, corr2, s);
+                            opt->beta1, opt->beta2, opt->eps, opt->weight_decay, corr1, corr2, s, w16);
             else
-                launch_sgd(w, g, cnt, opt->lr, opt->weight_decay, s);
+                launch_sgd(w, g, cnt, opt->lr, opt->weight_decay, s, w16);
         }
     return check_launch(c, "gnn_optimizer_step");
 }

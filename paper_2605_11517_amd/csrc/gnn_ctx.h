@@ -92,6 +92,7 @@ struct gnn_ctx {
     std::vector<const char*> w;          // W, W_s: dtype; b: fp32
     std::vector<float*> gw;
     std::vector<float*> opt_m, opt_v;    // Adam moments, bound by gnn_bind_optimizer
+    std::vector<float*> master;          // bfloat16 storage: fp32 copies of W, W_s the optimizer updates
     float dropout_p = 0.f;               // training: dropout rate after hidden activations
     uint64_t dropout_seed = 0;
     int64_t dropout_epoch = 0;

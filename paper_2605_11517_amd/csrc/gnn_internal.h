@@ -313,9 +313,12 @@ void launch_pad_rows(float* dst, const float* src, int64_t rows, int32_t d, int3
 // of row r), and the optimizer steps on one fp32 parameter tensor.
 void launch_dropout(void* a, int is_bf16, const int32_t* orig_of_row, int64_t rows, int32_t d,
                     uint64_t key, uint32_t threshold, float scale, hipStream_t s);
+// w16 (may be null): bfloat16 copy of the updated values, rounded to nearest even
 void launch_adam(float* w, const float* g, float* m, float* v, int64_t n, float lr, float beta1,
-                 float beta2, float eps, float weight_decay, float corr1, float corr2, hipStream_t s);
-void launch_sgd(float* w, const float* g, int64_t n, float lr, float weight_decay, hipStream_t s);
+                 float beta2, float eps, float weight_decay, float corr1, float corr2, hipStream_t s,
+                 void* w16 = nullptr);
+void launch_sgd(float* w, const float* g, int64_t n, float lr, float weight_decay, hipStream_t s,
+                void* w16 = nullptr);
 
 // Step 1 of one iteration of the switching-aware partitioner for every vertex: first and second
 // preference (second = -1 if there is none) from the assignment `part` and the partition sizes;

@@ -479,10 +479,18 @@ __global__ __launch_bounds__(kBlock) void k_pad_rows(float* __restrict__ dst, co
 }
 
 // One optimizer step over a parameter tensor of n floats.
+// fp32 -> bfloat16, round to nearest even (the rounding of k_to_bf16)
+__device__ inline uint16_t bf16_rne(float f)
+{
+    const uint32_t b = __float_as_uint(f);
+    return (uint16_t)((b + 0x7FFFu + ((b >> 16) & 1u)) >> 16);
+}
+
 __global__ __launch_bounds__(kBlock) void k_adam(float* __restrict__ w, const float* __restrict__ g,
                                                  float* __restrict__ m, float* __restrict__ v, int64_t n,
                                                  float lr, float beta1, float beta2, float eps,
-                                                 float weight_decay, float corr1, float corr2)
+                                                 float weight_decay, float corr1, float corr2,
+                                                 uint16_t* __restrict__ w16)
 {
     const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (i >= n) return;
@@ -492,16 +500,21 @@ __global__ __launch_bounds__(kBlock) void k_adam(float* __restrict__ w, const fl
     const float vi = beta2 * v[i] + (1.f - beta2) * gi * gi;
     m[i] = mi;
     v[i] = vi;
-    w[i] = wi - lr * (mi * corr1) / (sqrtf(vi * corr2) + eps);
+    const float wn = wi - lr * (mi * corr1) / (sqrtf(vi * corr2) + eps);
+    w[i] = wn;
+    if (w16) w16[i] = bf16_rne(wn);
 }
 
 __global__ __launch_bounds__(kBlock) void k_sgd(float* __restrict__ w, const float* __restrict__ g,
-                                                int64_t n, float lr, float weight_decay)
+                                                int64_t n, float lr, float weight_decay,
+                                                uint16_t* __restrict__ w16)
 {
     const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (i >= n) return;
     const float wi = w[i];
-    w[i] = wi - lr * (g[i] + weight_decay * wi);
+    const float wn = wi - lr * (g[i] + weight_decay * wi);
+    w[i] = wn;
+    if (w16) w16[i] = bf16_rne(wn);
 }
 
 }  // namespace
@@ -695,18 +708,19 @@ void launch_pad_rows(float* dst, const float* src, int64_t rows, int32_t d, int3
 }
 
 void launch_adam(float* w, const float* g, float* m, float* v, int64_t n, float lr, float beta1,
-                 float beta2, float eps, float weight_decay, float corr1, float corr2, hipStream_t s)
+                 float beta2, float eps, float weight_decay, float corr1, float corr2, hipStream_t s,
+                 void* w16)
 {
     if (n <= 0) return;
     hipLaunchKernelGGL(k_adam, dim3((unsigned)((n + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, w, g, m, v,
-                       n, lr, beta1, beta2, eps, weight_decay, corr1, corr2);
+                       n, lr, beta1, beta2, eps, weight_decay, corr1, corr2, (uint16_t*)w16);
 }
 
-void launch_sgd(float* w, const float* g, int64_t n, float lr, float weight_decay, hipStream_t s)
+void launch_sgd(float* w, const float* g, int64_t n, float lr, float weight_decay, hipStream_t s, void* w16)
 {
     if (n <= 0) return;
     hipLaunchKernelGGL(k_sgd, dim3((unsigned)((n + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, w, g, n, lr,
-                       weight_decay);
+                       weight_decay, (uint16_t*)w16);
 }
 
 }  // namespace gnnmi

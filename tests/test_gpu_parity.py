@@ -930,6 +930,77 @@ def test_dropout_epoch_and_training_steps_match_oracle(model, dims, dropout):
         say("  %s losses %s" % (opt, ["%.5f" % x for x in losses]))
 
 
+@pytest.mark.parametrize("model,dims", [("gcn", (64, 128, 64, 16)), ("sage", (72, 136, 8))])
+def test_bf16_training_steps_fp32_master_copies(model, dims):
+    """bfloat16 storage: the optimizer steps fp32 master copies of the matrices and the bound
+    matrices receive their rounding.  The step itself is checked exactly from the path's own
+    gradients (a bf16 gradient near zero can have either sign, which Adam turns into a whole
+    learning rate); plain SGD, linear in the gradient, is followed over three epochs against the
+    oracle's training with rounded weights."""
+    say("case bf16 training %s %s" % (model, dims))
+    from paper_2605_11517_amd import Session, GnnError
+    from paper_2605_11517_amd.binding import make_optimizer
+    from synth import to_bf16_grid
+    n, k = 3000, 4
+    L = len(dims) - 1
+    rowptr, colidx = small_graph(n, 30000, seed=41, symmetric=True, self_loops=False)
+    cfg = dict(model=model, dims=dims, seed=5, train_frac=0.5)
+    X, y, m, w = make_inputs(cfg, n)
+    X = to_bf16_grid(X)
+    # the master copies start off the bf16 grid
+    s = Session(model, dims, rowptr, colidx, k, "lp", 3, X, w, y, m, dtype="bf16")
+    opt = make_optimizer("adam", 0.01, 0.9, 0.999, 1e-8, 0.01)
+    s.epoch()
+    with pytest.raises(GnnError) as e:
+        s.ctx.optimizer_step(opt, 1, s.stream)              # no master copies yet
+    assert e.value.status == 4
+    import torch
+    t = torch
+    s.opt_m = [None if x is None else t.zeros(x.shape, dtype=t.float32, device=s.dev) for x in s.w]
+    s.opt_v = [None if x is None else t.zeros(x.shape, dtype=t.float32, device=s.dev) for x in s.w]
+    ptr = lambda x: x.data_ptr() if x is not None else None
+    s.ctx.bind_optimizer([ptr(x) for x in s.opt_m], [ptr(x) for x in s.opt_v])
+    s.bind_master_weights()
+    before, grads = s.master_weights(), s.results()
+    for l in range(L):                                       # bound matrices = rounding of the masters
+        assert np.array_equal(s.weights()[l]["W"], to_bf16_grid(before[l]["W"]))
+    s.ctx.optimizer_step(opt, 1, s.stream)
+    torch.cuda.synchronize()
+    after, bound = s.master_weights(), s.weights()
+    flat = lambda ws: [None if x is None else np.asarray(x, dtype=np.float64)
+                       for q in ws for x in (q["W"], q["Ws"], q["b"])]
+    g = [None if x is None else np.asarray(x, dtype=np.float64)
+         for l in range(L) for x in (grads["gW"][l], grads["gWs"][l], grads["gb"][l])]
+    ref, _, _ = og.adam_step(flat(before), g, [None if x is None else np.zeros_like(x) for x in flat(before)],
+                             [None if x is None else np.zeros_like(x) for x in flat(before)], 1, 0.01,
+                             weight_decay=0.01)
+    for l in range(L):
+        for j, key in enumerate(("W", "Ws", "b")):
+            if ref[3 * l + j] is None:
+                continue
+            assert rel_err(after[l][key], ref[3 * l + j]) <= 1e-5, (l, key)
+            assert not np.array_equal(after[l][key], before[l][key])
+            if key != "b":                                   # bit-exact rounding of the fp32 master
+                assert np.array_equal(bound[l][key], to_bf16_grid(after[l][key])), (l, key)
+    # three epochs of SGD from the start against the oracle
+    s = Session(model, dims, rowptr, colidx, k, "lp", 3, X, w, y, m, dtype="bf16")
+    losses = s.train(3, optimizer="sgd", lr=0.05, weight_decay=0.01)
+    ref_losses, ref_w, _ = og.train(model, rowptr, colidx, dims, X, w, y, m, epochs=3, optimizer="sgd",
+                                    lr=0.05, weight_decay=0.01, weight_round=to_bf16_grid)
+    for a, b in zip(losses, ref_losses):
+        assert abs(a - b) <= BF16_TOL * abs(b), (losses, ref_losses)
+    assert losses[2] < losses[0]
+    got_w = s.master_weights()
+    for l in range(L):
+        for key in ("W", "Ws", "b"):
+            if ref_w[l][key] is not None:
+                # against the movement of the weights, not their size: three steps move them little
+                moved = np.abs(np.asarray(ref_w[l][key]) - np.asarray(w[l][key], dtype=np.float64)).max()
+                err = np.abs(got_w[l][key] - ref_w[l][key]).max()
+                assert err <= BF16_TOL * max(moved, 1e-30) + 1e-6 * np.abs(ref_w[l][key]).max(), (l, key, err, moved)
+    say("  sgd losses %s (oracle %s)" % (["%.5f" % x for x in losses], ["%.5f" % x for x in ref_losses]))
+
+
 @pytest.mark.parametrize("name,dims", [("tiny", None),                      # gcn 64 -> 64 -> 16
                                        ("mini_sage", (24, 32, 12, 7)),      # two narrowing layers, padded width
                                        ("mini_sage", (16, 40, 40, 40, 6)),  # equal widths: saves the recompute
