@@ -40,7 +40,7 @@ def padded_width(d):
 
 
 def algorithmic_bytes(stats, dims, model, n_parts, es=4, fused_scatter=False, xf=None, pad=padded_width,
-                      masked=None):
+                      masked=None, first_touch=False):
     """HBM bytes the method has to move per epoch, by kernel class (lower bound: every needed
     source row is read once per partition).  es = bytes per stored activation (4 fp32, 2 bf16);
     gradients of activations are always fp32.  xf[l-1]: layer l transforms first, so it
@@ -48,7 +48,9 @@ def algorithmic_bytes(stats, dims, model, n_parts, es=4, fused_scatter=False, xf
     forward and once backward, with no regather and no recompute.  masked = (entries, rows,
     train vertices) of the output layer's transposed operator over train vertices, when in use:
     that pass then reads only those entries and the gradient rows of train vertices, and adds
-    onto `rows` rows."""
+    onto `rows` rows.  first_touch: the epoch stores the first contribution to a row of a
+    gradient array instead of adding it onto a zeroed one (every row once: n rows are written
+    without being read; not with the operator over train vertices)."""
     n, nnz, k = stats["n"], stats["nnz"], stats["k"]
     sum_r = n + stats["sum_boundary"]            # sum over partitions of |own_p| + |B_p|
     sum_b = stats["sum_boundary"]
@@ -72,6 +74,8 @@ def algorithmic_bytes(stats, dims, model, n_parts, es=4, fused_scatter=False, xf
                 out["spmm_t"] += 8 * m_e + 12 * (m_r + k) + m_v * hrow + 2 * m_r * row
             else:
                 out["spmm_t"] += 8 * nnz + 8 * (sum_r + k) + n * hrow + 2 * sum_r * row + 4 * sum_b
+                if first_touch and model != "gat":
+                    out["spmm_t"] -= n * row
             continue
         d = dims[l - 1]
         row = d * es
@@ -89,6 +93,8 @@ def algorithmic_bytes(stats, dims, model, n_parts, es=4, fused_scatter=False, xf
                 # transposed aggregation adds its rows straight onto their owners: read dZ once,
                 # read-modify-write every required row of grad A^{l-1}
                 out["spmm_t"] += 8 * nnz + 8 * (sum_r + k) + n * row + 2 * sum_r * grow + 4 * sum_b
+                if first_touch:
+                    out["spmm_t"] -= n * grow
             else:
                 out["spmm_t"] += 8 * nnz + 8 * (sum_r + k) + n * row + sum_r * grow
                 out["scatter"] += 3 * sum_r * grow + 4 * sum_b
@@ -367,8 +373,12 @@ def run_workload(name, args, steps, warmup, want_cpu):
         if paper_gather is not None:
             out["paper_order_gather"] = paper_gather
     if prof:
+        # resident epochs store the first contribution to a gradient row (GNNMI_FIRST_TOUCH=0: off)
+        first_touch = not budget and model != "gat" and os.environ.get("GNNMI_FIRST_TOUCH", "1")[:1] != "0"
+        out["config"]["gradient_rows_first_touch_store"] = first_touch
         ab = algorithmic_bytes(stats, dims, model, stats["k"], es,
-                               fused_scatter=prof.get("scatter", (0, 0))[1] == 0, xf=xf, masked=masked)
+                               fused_scatter=prof.get("scatter", (0, 0))[1] == 0, xf=xf, masked=masked,
+                               first_touch=first_touch)
         if gather_fused:
             ab["gather"] = 0                    # no staging copy is made
         fused = fused_layers(dims, xf, cfg["dtype"]) if model != "gat" else []

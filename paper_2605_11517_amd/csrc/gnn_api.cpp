@@ -62,6 +62,7 @@ void free_device(DevMeta& D)
     if (D.tw) (void)hipFree(D.tw);
     if (D.order) (void)hipFree(D.order);
     if (D.tperm) (void)hipFree(D.tperm);
+    if (D.first) (void)hipFree(D.first);
     free_plan(D.fwd);
     free_plan(D.bwd);
     D = DevMeta{};
@@ -133,10 +134,41 @@ gnn_status build_masked(gnn_ctx* c)
     return GNN_OK;
 }
 
+// HostMeta::first_bits: the partitions in schedule order, each one's rows (own, then B_p) marked
+// when nobody before them named the same row of the whole-graph array.
+void build_first_touch(HostMeta& M)
+{
+    M.first_off.assign((size_t)M.k + 1, 0);
+    for (int32_t p = 0; p < M.k; ++p) {
+        const int64_t rows = (M.off[(size_t)p + 1] - M.off[(size_t)p]) + (M.boff[(size_t)p + 1] - M.boff[(size_t)p]);
+        M.first_off[(size_t)p + 1] = M.first_off[(size_t)p] + (rows + 31) / 32;
+    }
+    M.first_bits.assign((size_t)M.first_off[(size_t)M.k], 0u);
+    std::vector<uint8_t> seen((size_t)M.n, 0);
+    for (int32_t t = 0; t < M.k; ++t) {
+        const int32_t p = M.sched[(size_t)t];
+        uint32_t* bits = M.first_bits.data() + M.first_off[(size_t)p];
+        const int64_t r0 = M.off[(size_t)p], np = M.off[(size_t)p + 1] - r0;
+        const int64_t b0 = M.boff[(size_t)p], nb = M.boff[(size_t)p + 1] - b0;
+        for (int64_t r = 0; r < np + nb; ++r) {
+            const int64_t row = r < np ? r0 + r : (int64_t)M.bnd[(size_t)(b0 + r - np)];
+            if (!seen[(size_t)row]) {
+                seen[(size_t)row] = 1;
+                bits[r >> 5] |= 1u << (r & 31);
+            }
+        }
+    }
+}
+
 gnn_status ensure_device(gnn_ctx* c)
 {
     if (c->D.ready) return GNN_OK;
     DevMeta& D = c->D;
+    try {
+        build_first_touch(c->M);
+    } catch (const std::bad_alloc&) {
+        return c->fail(GNN_ENOMEM, "out of host memory while marking first-touch rows");
+    }
     const HostMeta& M = c->M;
     hipError_t e = hipSuccess;
     auto step = [&](hipError_t r) { if (e == hipSuccess) e = r; };
@@ -152,6 +184,7 @@ gnn_status ensure_device(gnn_ctx* c)
     step(upload(D.tw, M.tw));
     step(upload(D.order, M.order));
     step(upload(D.tperm, M.tperm));
+    step(upload(D.first, M.first_bits));
     step(upload_plan(D.fwd, M.plan_fwd));
     step(upload_plan(D.bwd, M.plan_bwd));
     if (e != hipSuccess) {
@@ -533,6 +566,7 @@ static TransposedOp transposed_op(gnn_ctx* c, int32_t layer, int32_t p)
     op.sc.n_own = np;
     op.sc.base_row = r0;
     op.sc.idx = c->D.bnd + M.boff[(size_t)p];
+    if (c->first_touch && c->D.first) op.sc.first = c->D.first + M.first_off[(size_t)p];
     return op;
 }
 
@@ -967,7 +1001,9 @@ void xf_transform_bwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own_c
 // Start of a transform-first layer's backward pass: grad H := 0 (it takes the buffer H was in).
 void xf_begin_bwd(gnn_ctx* c, int32_t layer, hipStream_t s)
 {
-    {
+    // (an epoch that lets first-touch rows store has nothing to zero, unless the operator is the
+    // output layer's over train vertices, which does not reach every row)
+    if (!(c->first_touch && c->D.first && !(layer == c->L && c->masked_transpose()))) {
         Timed t(c, s, GNN_K_OTHER);
         launch_fill_zero(c->ghbuf, c->M.n * (int64_t)c->padded(layer) * 4, s);
         // grad A^{l-1} needs no initialisation here: each of its rows is written once (by
@@ -1486,18 +1522,21 @@ gnn_status gnn_layer_bwd(gnn_ctx* c, int32_t layer, int32_t p, void* stream)
     const int64_t nb = M.boff[(size_t)p + 1] - M.boff[(size_t)p];
     const int32_t din = c->dims[(size_t)layer - 1], dout = c->dims[(size_t)layer];
 
-    // write-back buffer initialisation: first partition of this layer since gnn_loss
-    if (layer >= 2 && c->bwd_done[(size_t)layer] == 0) {
-        Timed t(c, s, GNN_K_OTHER);
-        launch_fill_zero(c->gact[(size_t)layer - 2], M.n * (int64_t)din * 4, s);
-    }
-    const char* act_own = c->act[(size_t)layer - 1] + r0 * (int64_t)dout * c->act_es(layer);
     // scatter-accumulate of the gathered-row gradient: fused into the transposed aggregation
     // (GNNMI_FUSE_SCATTER=0 keeps it a separate pass over a scratch copy)
     static const bool fuse = [] {
         const char* e = std::getenv("GNNMI_FUSE_SCATTER");
         return !(e && e[0] == '0');
     }();
+    // write-back buffer initialisation: first partition of this layer since gnn_loss (not when
+    // the epoch lets first-touch rows store; the operator over train vertices does not reach
+    // every row)
+    const bool stores_first = fuse && c->first_touch && c->D.first && !(layer == c->L && c->masked_transpose());
+    if (layer >= 2 && c->bwd_done[(size_t)layer] == 0 && !stores_first) {
+        Timed t(c, s, GNN_K_OTHER);
+        launch_fill_zero(c->gact[(size_t)layer - 2], M.n * (int64_t)din * 4, s);
+    }
+    const char* act_own = c->act[(size_t)layer - 1] + r0 * (int64_t)dout * c->act_es(layer);
     float* gprev = layer >= 2 ? c->gact[(size_t)layer - 2] : nullptr;
     const char* dY = compute_bwd(c, layer, p, c->layer_input(layer, r0),
                                  c->gact[(size_t)layer - 1] + r0 * dout, act_own, fuse ? gprev : nullptr, nullptr, s);
@@ -1632,6 +1671,17 @@ static gnn_status epoch_resident(gnn_ctx* c, void* stream, float* loss_out)
         }
     }
     if ((st = gnn_loss(c, stream)) != GNN_OK) return st;
+    // the partitions of a backward layer are walked in schedule order from here on: rows that are
+    // first to reach their row of a gradient array store, the others add
+    static const bool first_touch_on = [] {
+        const char* e = std::getenv("GNNMI_FIRST_TOUCH");
+        return !(e && e[0] == '0');
+    }();
+    struct FirstTouch {
+        gnn_ctx* c;
+        ~FirstTouch() { c->first_touch = false; }
+    } first_touch_scope{c};
+    c->first_touch = first_touch_on && c->model != GNN_GAT;
     bool wait_steps = false;          // the partitions of this layer wait for the side stream, step by step
     for (int32_t l = L; l >= 1; --l) {
         const bool xf = c->transform_first(l);

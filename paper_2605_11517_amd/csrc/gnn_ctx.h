@@ -25,6 +25,7 @@ struct DevMeta {
     float* tw = nullptr;
     int32_t* order = nullptr;
     int32_t* tperm = nullptr;
+    uint32_t* first = nullptr;   // HostMeta::first_bits
     struct Plan {
         int32_t* range_rows = nullptr;
         int32_t* seg_row = nullptr;
@@ -138,6 +139,11 @@ struct gnn_ctx {
     // The output layer's transposed aggregation runs over the operator entries of train vertices
     // only (the gradient of the loss is zero elsewhere); the sub-operator is built by gnn_bind
     bool masked_bwd = false;
+    // gnn_epoch, resident, while it walks the partitions of a backward layer in schedule order:
+    // the transposed aggregation stores the rows that are first to reach their output row and
+    // the target array is not zeroed beforehand (GNNMI_FIRST_TOUCH=0: zero and add as the
+    // per-partition entry points do, which may be called in any order)
+    bool first_touch = false;
     bool masked_transpose() const { return masked_bwd && !streaming() && model != GNN_GAT && D.masked_t.ready; }
     bool stream_xf_ok = false;               // set by update_stream_xf() once the partitions exist
     // bytes of the whole-graph buffers the transform-first layers (by the cost rule) would need

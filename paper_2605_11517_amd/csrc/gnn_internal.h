@@ -44,6 +44,12 @@ struct HostMeta {
     std::vector<int32_t> tperm;     // GAT: position of the entry in the forward operator, minus the
                                     // partition's first position
     std::vector<int32_t> sched;     // k: order in which an epoch walks the partitions
+    // Walking the partitions in that order, which rows of the transposed operator (own rows, then
+    // B_p) are the first to name their row of the whole-graph array: bit r of partition p's words
+    // (first_off[p] .. first_off[p + 1]) is set for such a row.  An epoch lets them store where
+    // the others add, and then needs no zeroed array to add onto.
+    std::vector<uint32_t> first_bits;
+    std::vector<int64_t> first_off;  // k+1, in 32-bit words
     gnn_stats stats{};
     int32_t part_iterations = 0;          // switching-aware partitioner: iterations run
     std::vector<double> part_objective;   // and the mean score per vertex of every state
@@ -131,6 +137,8 @@ struct SpmmScatter {
     int64_t n_own = -1;
     int64_t base_row = 0;
     const int32_t* idx = nullptr;
+    // optional: bit r set = row r is stored, not added (its output row holds nothing yet)
+    const uint32_t* first = nullptr;
     // applied to what is stored (after the add, if any): + bias[column], then max(., 0)
     const float* bias = nullptr;
     int relu = 0;

@@ -116,6 +116,7 @@ struct SpmmArgs {
     // map_base + r when r < map_n_own, else to row map_idx[r - map_n_own]; map_n_own < 0 = off
     int64_t map_n_own, map_base;
     const int32_t* map_idx;
+    const uint32_t* map_first;   // optional bit per row: set = store, do not add
     // applied to what is stored: + bias[column] (pointer already at this launch's first column),
     // then max(., 0)
     const float* bias;
@@ -124,6 +125,12 @@ struct SpmmArgs {
     {
         if (map_n_own < 0) return r;
         return r < map_n_own ? map_base + r : (int64_t)map_idx[r - map_n_own];
+    }
+    __device__ bool adds(int32_t r) const
+    {
+        if (map_n_own < 0) return false;
+        if (!map_first) return true;
+        return ((map_first[r >> 5] >> (r & 31)) & 1u) == 0u;
     }
 };
 
@@ -344,7 +351,7 @@ __global__ __launch_bounds__(kBlock) void k_spmm_items(const SpmmArgs g)
             for (int i = 0; i < EPV; ++i) acc[v][i] = 0.f;
         spmm_accumulate<TIn, G, NV, VEC>(g, e_begin, e_end, lane, acc);
         spmm_store<TOut, EPV, G, NV, VEC>(static_cast<TOut*>(g.out) + g.out_row(row) * (int64_t)g.ld, g.d,
-                                          lane, g.rowscale ? g.rowscale[row] : 1.f, acc, g.map_n_own >= 0,
+                                          lane, g.rowscale ? g.rowscale[row] : 1.f, acc, g.adds(row),
                                           g.bias, g.relu != 0);
     }
 }
@@ -454,7 +461,7 @@ __global__ __launch_bounds__(kBlock) void k_spmm_slots(const SpmmArgs g, int32_t
         const float sc = g.rowscale ? g.rowscale[row] : 1.f;
         TOut* o = static_cast<TOut*>(g.out) + g.out_row(row) * (int64_t)g.ld + coff;
         constexpr int OPV = Elem<TOut>::EPV;
-        const bool add = g.map_n_own >= 0;     // fused scatter-accumulate (fp32 output): one slot per row
+        const bool add = g.adds(row);     // fused scatter-accumulate (fp32 output): one slot per row
 #pragma unroll
         for (int h = 0; h < EPV / OPV; ++h) {
             float f[OPV];
@@ -618,7 +625,7 @@ __global__ __launch_bounds__(kBlock) void k_spmm_short(const SpmmArgs g, int32_t
         const float sc = g.rowscale ? g.rowscale[row] : 1.f;
         TOut* orow = static_cast<TOut*>(g.out) + g.out_row(row) * (int64_t)g.ld;
         constexpr int OPV = Elem<TOut>::EPV;
-        const bool add = g.map_n_own >= 0;     // fused scatter-accumulate (fp32 output): one slot per row
+        const bool add = g.adds(row);     // fused scatter-accumulate (fp32 output): one slot per row
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
             if (!live[v]) continue;
@@ -930,7 +937,7 @@ __global__ __launch_bounds__(kBlock) void k_spmm_long_reduce(const SpmmArgs g)
     const float sc = g.rowscale ? g.rowscale[row] : 1.f;
     const int32_t cb = blockIdx.y * 256;          // first column of this block
     TOut* out = static_cast<TOut*>(g.out) + g.out_row(row) * (int64_t)g.ld;
-    const bool add = g.map_n_own >= 0;
+    const bool add = g.adds(row);
     if (VEC) {
         const int32_t c = cb + lane * 4;
         if (c >= g.d) return;
@@ -1077,7 +1084,7 @@ void spmm_typed(const int64_t* rp, const int32_t* col, const float* w, const flo
             g.rp = rp; g.col = col; g.w = w; g.rowscale = rowscale;
             g.a_rows = a_rows; g.n_a = n_a; g.b_rows = b_rows; g.out = out; g.d = d; g.ld = d;
             g.it = items; g.partial = partial;
-            g.map_n_own = -1; g.map_base = 0; g.map_idx = nullptr;
+            g.map_n_own = -1; g.map_base = 0; g.map_idx = nullptr; g.map_first = nullptr;
             g.bias = sc.bias; g.relu = sc.relu;
             const dim3 grid((unsigned)(blocks * ns));
             const bool few2s = items.avg_len > 0.f && items.avg_len < short_rows_max();
@@ -1115,7 +1122,7 @@ void spmm_typed(const int64_t* rp, const int32_t* col, const float* w, const flo
         g.rp = rp; g.col = col; g.w = w; g.rowscale = rowscale;
         g.a_rows = a_rows; g.n_a = n_a; g.b_rows = b_rows; g.out = out; g.d = d; g.ld = d;
         g.it = items; g.partial = partial;
-        g.map_n_own = sc.n_own; g.map_base = sc.base_row; g.map_idx = sc.idx;
+        g.map_n_own = sc.n_own; g.map_base = sc.base_row; g.map_idx = sc.idx; g.map_first = sc.first;
         g.bias = sc.bias; g.relu = sc.relu;
         if (few) hipLaunchKernelGGL((k_spmm_short<TIn, TOut, 32, 4, 2>), dim3((unsigned)blocks), dim3(kBlock), 0, s, g, 1);
         else hipLaunchKernelGGL((k_spmm_short<TIn, TOut, 32, 4, 2, false>), dim3((unsigned)blocks), dim3(kBlock), 0, s, g, 1);
@@ -1131,7 +1138,7 @@ void spmm_typed(const int64_t* rp, const int32_t* col, const float* w, const flo
         g.rp = rp; g.col = col; g.w = w; g.rowscale = rowscale;
         g.a_rows = a_rows; g.n_a = n_a; g.b_rows = b_rows; g.out = out; g.d = d; g.ld = d;
         g.it = items; g.partial = partial;
-        g.map_n_own = sc.n_own; g.map_base = sc.base_row; g.map_idx = sc.idx;
+        g.map_n_own = sc.n_own; g.map_base = sc.base_row; g.map_idx = sc.idx; g.map_first = sc.first;
         g.bias = sc.bias; g.relu = sc.relu;
         const dim3 grid1((unsigned)blocks);
         if (G == 4) hipLaunchKernelGGL((k_spmm_slots<TIn, TOut, 4>), grid1, dim3(kBlock), 0, s, g, 1);
@@ -1159,7 +1166,7 @@ void spmm_typed(const int64_t* rp, const int32_t* col, const float* w, const flo
         g.b_rows = b_rows ? static_cast<const TIn*>(b_rows) + c0 : nullptr;
         g.out = static_cast<TOut*>(out) + c0; g.d = dc; g.ld = d; g.it = items;
         g.partial = partial + c0;
-        g.map_n_own = sc.n_own; g.map_base = sc.base_row; g.map_idx = sc.idx;
+        g.map_n_own = sc.n_own; g.map_base = sc.base_row; g.map_idx = sc.idx; g.map_first = sc.first;
         g.bias = sc.bias ? sc.bias + c0 : nullptr; g.relu = sc.relu;
         const int nv = (dc + EPV - 1) / EPV;  // 16-byte vectors per row in this block
 #define GNN_SPMM(G, NV, VEC) \
@@ -1190,7 +1197,7 @@ void spmm_reduce_typed(const float* rowscale, void* out, int32_t d, const SpmmIt
     const int wpb = kBlock / kWave;
     SpmmArgs g{};
     g.rowscale = rowscale; g.out = out; g.d = d; g.ld = d; g.it = items; g.partial = partial;
-    g.map_n_own = sc.n_own; g.map_base = sc.base_row; g.map_idx = sc.idx;
+    g.map_n_own = sc.n_own; g.map_base = sc.base_row; g.map_idx = sc.idx; g.map_first = sc.first;
     g.bias = sc.bias; g.relu = sc.relu;
     const dim3 rgrid((unsigned)((items.nlong + wpb - 1) / wpb), (unsigned)((d + 255) / 256));
     if (d % 4 == 0) hipLaunchKernelGGL((k_spmm_long_reduce<TOut, true>), rgrid, dim3(kBlock), 0, s, g);
@@ -1247,7 +1254,7 @@ void launch_spmm_gemm_fused(const int64_t* rp, const int32_t* col, const float* 
     g.sp.rp = rp; g.sp.col = col; g.sp.w = w; g.sp.rowscale = rowscale;
     g.sp.a_rows = a_rows; g.sp.n_a = n_a; g.sp.b_rows = b_rows; g.sp.out = nullptr;
     g.sp.d = din; g.sp.ld = din; g.sp.it = items; g.sp.partial = partial;
-    g.sp.map_n_own = -1; g.sp.map_base = 0; g.sp.map_idx = nullptr; g.sp.bias = nullptr; g.sp.relu = 0;
+    g.sp.map_n_own = -1; g.sp.map_base = 0; g.sp.map_idx = nullptr; g.sp.map_first = nullptr; g.sp.bias = nullptr; g.sp.relu = 0;
     g.zlong = zlong; g.xself = xself; g.w = W; g.ws = Ws; g.bias = bias; g.y = y; g.dout = dout; g.relu = relu;
     g.kp = din + 1;
     const size_t lds = (size_t)64 * (size_t)g.kp * sizeof(float) * (xself ? 2 : 1);

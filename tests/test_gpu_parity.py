@@ -930,6 +930,66 @@ def test_dropout_epoch_and_training_steps_match_oracle(model, dims, dropout):
         say("  %s losses %s" % (opt, ["%.5f" % x for x in losses]))
 
 
+@pytest.mark.parametrize("name,dims,order", [("mini_sage", (24, 32, 12, 7), "auto"),
+                                             ("mini_sage", (16, 40, 40, 6), "aggregate"),
+                                             ("mini_gcn_directed", (20, 9, 9, 5), "auto"),
+                                             ("tiny", None, "aggregate")])
+def test_epoch_needs_no_zeroed_gradient_arrays(name, dims, order):
+    """gnn_epoch lets the rows that are first to reach a row of a gradient array store and zeroes
+    nothing beforehand; the per-partition entry points zero and add.  Same values either way, and
+    no row may be left as it was: the scratch (grad H lives there) and the gradient arrays are
+    filled with NaN bit patterns before the epoch."""
+    say("case first-touch %s %s %s" % (name, dims, order))
+    import torch
+    from paper_2605_11517_amd import Session
+    over = {} if dims is None else {"dims": dims}
+    cfg, rowptr, colidx = make_config(name, **over)
+    n, dims, model, k = cfg["n"], cfg["dims"], cfg["model"], cfg["k"]
+    L = len(dims) - 1
+    X, y, m, w = make_inputs(cfg, n)
+    ref = og.epoch(model, rowptr, colidx, dims, X, w, y, m)
+    for masked in (False, True):
+        s = Session(model, dims, rowptr, colidx, k, cfg["part"], cfg["seed"], X, w, y, m, layer_order=order,
+                    masked_backward=masked)
+        s.scratch.fill_(0xFF)
+        for g in s.gact:
+            g.view(torch.uint8).fill_(0xFF)
+        torch.cuda.synchronize()
+        loss = s.epoch()
+        r1 = s.results()
+        assert abs(loss - ref["loss"]) <= TOL * abs(ref["loss"])
+        compare(r1, ref, model, tag="first-touch %s masked=%s" % (name, masked))
+        # the per-partition entry points (zero, then add) give the same values
+        st = s.stream
+        xf = [s.ctx.layer_is_transform_first(l) for l in range(1, L + 1)]
+        for g in s.gw:
+            if g is not None:
+                g.zero_()
+        torch.cuda.synchronize()
+        for l in range(1, L + 1):
+            if xf[l - 1]:
+                for p in range(k):
+                    s.ctx.layer_transform_fwd(l, p, st)
+            for p in range(k):
+                s.ctx.gather_boundary(l, p, st)
+                s.ctx.layer_fwd(l, p, st)
+        s.ctx.loss(st)
+        for l in range(L, 0, -1):
+            for p in range(k):
+                if not xf[l - 1]:
+                    s.ctx.gather_boundary(l, p, st)
+                s.ctx.layer_bwd(l, p, st)
+            if xf[l - 1]:
+                for p in range(k):
+                    s.ctx.layer_transform_bwd(l, p, st)
+        torch.cuda.synchronize()
+        r2 = s.results()
+        for key in ("gact", "gW", "gWs", "gb"):
+            for a, b in zip(r1[key], r2[key]):
+                if a is not None:
+                    assert rel_err(a, b) <= 1e-6, (key, masked)      # another order of additions
+
+
 @pytest.mark.parametrize("model,dims", [("gcn", (64, 128, 64, 16)), ("sage", (72, 136, 8))])
 def test_bf16_training_steps_fp32_master_copies(model, dims):
     """bfloat16 storage: the optimizer steps fp32 master copies of the matrices and the bound
