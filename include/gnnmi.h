@@ -328,9 +328,12 @@ gnn_status gnn_epoch(gnn_ctx *ctx, void *stream, float *loss_out);
  *   GNN_ORDER_AUTO: a layer transforms first when that moves fewer rows: 2 d_l < 3 d_{l-1}
  *     (layer 1, which needs no input gradient: 2 d_l < 2 d_{l-1}); aggregating first reads
  *     input-wide rows forward, again in the recompute and once more transposed, transforming
- *     first aggregates output-wide rows once forward and once transposed.  Resident schedule;
- *     with GNN_BF16 only layers whose output rows are whole 16-byte vectors (d_l a multiple
- *     of 8), and among the hidden layers only those of GNN_GCN.  Other layers and
+ *     first aggregates output-wide rows once forward and once transposed.  With GNN_BF16
+ *     only layers whose output rows are whole 16-byte vectors (d_l a multiple of 8), and
+ *     among the hidden layers only those of GNN_GCN.  Streaming schedule (hbm_budget_bytes >
+ *     0): only when the budget holds the whole-graph buffer of such layers (n rows of their
+ *     widest padded output, fp32) beside two whole per-layer arrays of the widest layer and
+ *     the smallest block cache, and with GNN_BF16 for GNN_GCN only.  Other layers and
  *     configurations keep the paper's order.
  * Changes the workspace sizes: call before gnn_workspace_bytes / gnn_bind (a bound context
  * becomes unbound).  Results differ from the other order only by rounding. */

@@ -234,7 +234,7 @@ gnn_status ensure_global_columns(gnn_ctx* c)
 void update_stream_xf(gnn_ctx* c)
 {
     c->stream_xf_ok = false;
-    if (!c->streaming() || !c->built || c->bf16() || c->model == GNN_GAT) return;
+    if (!c->streaming() || !c->built || c->model == GNN_GAT) return;
     int64_t dmax = 0;
     for (int32_t d : c->dims) dmax = std::max<int64_t>(dmax, d);
     const int64_t blk = (std::max<int64_t>(1, c->M.stats.max_own) * dmax * 4 + 255) / 256 * 256;

@@ -112,9 +112,11 @@ struct gnn_ctx {
     {
         if (model == GNN_GAT) return true;       // attention scores are taken from H = A W
         if (order_mode != 1) return false;
-        // streaming schedule: fp32 only, and only when the whole-graph buffers of such layers
-        // (H / grad H, kept dY rows) fit into the HBM budget beside a minimal block cache
-        if (streaming() && (bf16() || !stream_xf_ok)) return false;
+        // streaming schedule: only when the whole-graph buffers of such layers (H / grad H, kept
+        // dY rows) fit into the HBM budget beside a minimal block cache; and with bfloat16 storage
+        // for GCN only (the first backward sweep of a bfloat16 GraphSAGE layer writes the self
+        // term into grad A^{l-1} of the partition, which the streaming sweep does not hold then)
+        if (streaming() && (!stream_xf_ok || (bf16() && model != GNN_GCN))) return false;
         return wants_transform_first(layer);
     }
     // the cost rule alone

@@ -705,14 +705,21 @@ def test_storage_tier_below_host_memory_is_bit_identical_to_resident(case, tmp_p
     assert not any(f.name.startswith("array_") for f in tmp_path.iterdir())
 
 
-@pytest.mark.parametrize("name,dims,extra", [
-    ("mini_sage", (100, 256, 256, 47), 1.0),            # hidden GraphSAGE layer takes its dY rows twice; padded 48-wide output
-    ("mini_sage", (100, 256, 256, 47), 3.0),
-    ("mini_gcn_directed", (128, 128, 128, 172), 1.0),
-    ("tiny", (64, 64, 16), 2.0),
-    ("mini_sage", (64, 32, 32, 8), 1.0),                # every layer transforms first
+@pytest.mark.parametrize("name,dims,extra,dtype", [
+    ("mini_sage", (100, 256, 256, 47), 1.0, "f32"),     # hidden GraphSAGE layer takes its dY rows twice; padded 48-wide output
+    ("mini_sage", (100, 256, 256, 47), 3.0, "f32"),
+    ("mini_gcn_directed", (128, 128, 128, 172), 1.0, "f32"),
+    ("tiny", (64, 64, 16), 2.0, "f32"),
+    ("mini_sage", (64, 32, 32, 8), 1.0, "f32"),         # every layer transforms first
+    ("mini_gcn_directed", (128, 64, 64, 16), 1.0, "bf16"),   # bfloat16 storage: H in bf16, its gradient fp32
+    # bfloat16 GraphSAGE keeps the paper's order when streaming: the first backward sweep of such
+    # a layer adds the self term into grad A^{l-1} of the partition, and the streaming sweep hands
+    # it no such block (a null pointer: this case faulted the GPU when the order was allowed)
+    pytest.param("mini_sage", (72, 136, 8), 2.0, "bf16",
+                 marks=pytest.mark.skip(reason="bfloat16 GraphSAGE does not transform first in the streaming "
+                                               "schedule (the library keeps the paper's order there)")),
 ])
-def test_streaming_transform_first_layers_are_bit_identical_to_resident(name, dims, extra):
+def test_streaming_transform_first_layers_are_bit_identical_to_resident(name, dims, extra, dtype):
     """Layer order by rows moved in the streaming schedule: the whole-graph buffer of the
     transform-first layers comes out of the HBM budget, the rest is the pool (`extra` times the
     least the rule asks for: two whole arrays of the widest layer and the smallest block cache).
@@ -724,8 +731,15 @@ def test_streaming_transform_first_layers_are_bit_identical_to_resident(name, di
     cfg = dict(cfg, dims=dims)
     n = cfg["n"]
     X, y, m, w = make_inputs(cfg, n)
+    if dtype == "bf16":
+        from synth import to_bf16_grid
+        X = to_bf16_grid(X)
+        for layer in w:
+            layer["W"] = to_bf16_grid(layer["W"])
+            if layer["Ws"] is not None:
+                layer["Ws"] = to_bf16_grid(layer["Ws"])
     res = Session(cfg["model"], dims, rowptr, colidx, cfg["k"], cfg["part"], cfg["seed"], X, w, y, m,
-                  layer_order="auto")
+                  layer_order="auto", dtype=dtype)
     L = len(dims) - 1
     order = [res.ctx.layer_is_transform_first(l) for l in range(1, L + 1)]
     assert any(order)
@@ -740,7 +754,7 @@ def test_streaming_transform_first_layers_are_bit_identical_to_resident(name, di
     # room for two whole arrays of the widest layer beside the buffer, plus the smallest block cache
     minimum = 2 * cfg["k"] * blk + 4 * blk
     s = Session(cfg["model"], dims, rowptr, colidx, cfg["k"], cfg["part"], cfg["seed"], X, w, y, m,
-                layer_order="auto", hbm_budget_bytes=int(xf_bytes + minimum * extra))
+                layer_order="auto", hbm_budget_bytes=int(xf_bytes + minimum * extra), dtype=dtype)
     assert [s.ctx.layer_is_transform_first(l) for l in range(1, L + 1)] == order
     for rep in range(2):
         assert s.epoch() == loss_res
@@ -751,6 +765,8 @@ def test_streaming_transform_first_layers_are_bit_identical_to_resident(name, di
                     assert b is None
                     continue
                 assert np.array_equal(a, b), (rep, key, l)
+    if dtype == "bf16":
+        return      # the resident bfloat16 epoch is what the oracle is compared with elsewhere
     ref = og.epoch(cfg["model"], rowptr, colidx, dims, X, w, y, m)
     compare(got, ref, cfg["model"], tag="streaming transform-first " + name)
     # 256 bytes short of that: every layer keeps the paper's order
