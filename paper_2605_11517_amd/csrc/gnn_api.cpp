@@ -158,6 +158,17 @@ void build_first_touch(HostMeta& M)
             }
         }
     }
+    // the short rows of the transposed plan carry the same mark in the top bit of their list
+    // entry, where the kernels that walk that list find it without another load
+    HostMeta::Plan& B = M.plan_bwd;
+    for (int32_t p = 0; p < M.k && !B.rows_off.empty(); ++p) {
+        const uint32_t* bits = M.first_bits.data() + M.first_off[(size_t)p];
+        for (int64_t i = B.rows_off[(size_t)p]; i < B.rows_off[(size_t)p + 1]; ++i) {
+            const int32_t r = B.rows_sorted[(size_t)i] & 0x7FFFFFFF;
+            const bool first = (bits[r >> 5] >> (r & 31)) & 1u;
+            B.rows_sorted[(size_t)i] = first ? (int32_t)((uint32_t)r | 0x80000000u) : r;
+        }
+    }
 }
 
 gnn_status ensure_device(gnn_ctx* c)

@@ -393,11 +393,16 @@ __global__ __launch_bounds__(kBlock) void k_spmm_slots(const SpmmArgs g, int32_t
     int64_t e_begin = 0;
     int32_t len = 0;
     int32_t row = -1;
+    bool first_row = false;
     if (item < g.it.nsegs) {
         e_begin = g.it.seg_begin[item];
         len = g.it.seg_len[item];
     } else if (item < g.it.nsegs + g.it.nshort) {
-        row = g.it.rows_sorted[item - g.it.nsegs];
+        // (the top bit of an entry of the transposed plan's list marks a row that is first to
+        // reach its output row; it counts only where map_first is given)
+        const int32_t listed = g.it.rows_sorted[item - g.it.nsegs];
+        row = listed & 0x7FFFFFFF;
+        first_row = listed < 0;
         e_begin = g.rp[row];
         len = (int32_t)(g.rp[row + 1] - e_begin);
     }
@@ -461,7 +466,7 @@ __global__ __launch_bounds__(kBlock) void k_spmm_slots(const SpmmArgs g, int32_t
         const float sc = g.rowscale ? g.rowscale[row] : 1.f;
         TOut* o = static_cast<TOut*>(g.out) + g.out_row(row) * (int64_t)g.ld + coff;
         constexpr int OPV = Elem<TOut>::EPV;
-        const bool add = g.adds(row);     // fused scatter-accumulate (fp32 output): one slot per row
+        const bool add = g.map_n_own >= 0 && !(g.map_first && first_row);   // fused scatter-accumulate (fp32 output): one slot per row
 #pragma unroll
         for (int h = 0; h < EPV / OPV; ++h) {
             float f[OPV];
@@ -525,11 +530,16 @@ __global__ __launch_bounds__(kBlock) void k_spmm_short(const SpmmArgs g, int32_t
     int64_t e_begin = 0;
     int32_t len = 0;
     int32_t row = -1;
+    bool first_row = false;
     if (item < g.it.nsegs) {
         e_begin = g.it.seg_begin[item];
         len = g.it.seg_len[item];
     } else if (item < g.it.nsegs + g.it.nshort) {
-        row = g.it.rows_sorted[item - g.it.nsegs];
+        // (the top bit of an entry of the transposed plan's list marks a row that is first to
+        // reach its output row; it counts only where map_first is given)
+        const int32_t listed = g.it.rows_sorted[item - g.it.nsegs];
+        row = listed & 0x7FFFFFFF;
+        first_row = listed < 0;
         e_begin = g.rp[row];
         len = (int32_t)(g.rp[row + 1] - e_begin);
     }
@@ -625,7 +635,7 @@ __global__ __launch_bounds__(kBlock) void k_spmm_short(const SpmmArgs g, int32_t
         const float sc = g.rowscale ? g.rowscale[row] : 1.f;
         TOut* orow = static_cast<TOut*>(g.out) + g.out_row(row) * (int64_t)g.ld;
         constexpr int OPV = Elem<TOut>::EPV;
-        const bool add = g.adds(row);     // fused scatter-accumulate (fp32 output): one slot per row
+        const bool add = g.map_n_own >= 0 && !(g.map_first && first_row);   // fused scatter-accumulate (fp32 output): one slot per row
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
             if (!live[v]) continue;
@@ -780,7 +790,7 @@ __global__ __launch_bounds__(kBlock) void k_agg_gemm(const FusedArgs g)
                 row = sp.it.long_row[li];
                 is_long = true;
             } else {
-                row = sp.it.rows_sorted[li];
+                row = sp.it.rows_sorted[li] & 0x7FFFFFFF;
                 e_begin = sp.rp[row];
                 len = (int32_t)(sp.rp[row + 1] - e_begin);
             }
@@ -898,7 +908,7 @@ __global__ __launch_bounds__(kBlock) void k_agg_gemm(const FusedArgs g)
     if (threadIdx.x < TM) {
         const int64_t li = tile0 + threadIdx.x;
         int32_t row = -1;
-        if (li < nrows) row = g.long_only ? sp.it.long_row[li] : sp.it.rows_sorted[li];
+        if (li < nrows) row = g.long_only ? sp.it.long_row[li] : (sp.it.rows_sorted[li] & 0x7FFFFFFF);
         tile_row[threadIdx.x] = row;
     }
     __syncthreads();
