@@ -55,7 +55,46 @@ __global__ __launch_bounds__(kBlock) void k_loss(const float* __restrict__ logit
             for (int j = lane; j < c; j += kWave) g[j] = 0.f;
         }
     }
-    for (int it = 0; it < kLossRowsPerWave; ++it) {
+    // the labels of the wavefront's train rows in one read as well
+    const int32_t my_label = (mine && ((train >> lane) & 1ull)) ? labels[v0 + lane] : 0;
+    constexpr int NX = 4;                   // up to 256 classes: a row is read once, into registers
+    for (int it = 0; c <= NX * kWave && it < kLossRowsPerWave; ++it) {
+        if (!((train >> it) & 1ull)) continue;
+        const int64_t v = v0 + it;
+        const float* x = logits + v * c;
+        float* g = grad + v * c;
+        float xv[NX];
+#pragma unroll
+        for (int u = 0; u < NX; ++u) {
+            const int j = lane + u * kWave;
+            xv[u] = j < c ? x[j] : -INFINITY;
+        }
+        // (same order of operations per lane as the general loop below: the same bits)
+        float mx = -INFINITY;
+#pragma unroll
+        for (int u = 0; u < NX; ++u) mx = fmaxf(mx, xv[u]);
+        mx = wave_max(mx);
+        float se = 0.f;
+#pragma unroll
+        for (int u = 0; u < NX; ++u)
+            if (lane + u * kWave < c) se += expf(xv[u] - mx);
+        se = wave_sum(se);
+        const float lse = mx + logf(se);
+        const int32_t y = __shfl(my_label, it, kWave);
+        float xy = 0.f;
+#pragma unroll
+        for (int u = 0; u < NX; ++u) {
+            const float cand = __shfl(xv[u], y & (kWave - 1), kWave);
+            if ((y >> 6) == u) xy = cand;
+        }
+        term += lse - xy;
+#pragma unroll
+        for (int u = 0; u < NX; ++u) {
+            const int j = lane + u * kWave;
+            if (j < c) g[j] = (expf(xv[u] - lse) - (j == y ? 1.f : 0.f)) * inv_count;
+        }
+    }
+    for (int it = 0; c > NX * kWave && it < kLossRowsPerWave; ++it) {
         if (!((train >> it) & 1ull)) continue;
         const int64_t v = v0 + it;
         const float* x = logits + v * c;
