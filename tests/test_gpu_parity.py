@@ -482,6 +482,9 @@ BF16_CASES = [
     # chip has CUs, so the persistent kernel's workgroups walk several tiles each (padding indices
     # in between, a 96-row tail, a 64-column tail), with 1, 5 and 8 K stages per tile
     ("gcn", (64, 320, 512, 16), 120000, 500000, True, 2, "random"),
+    # K = 2048: 32 K stages per tile, more than the sixteen chunks a parked tile is stored in, with
+    # 274 row tiles of one column tile (some workgroups take two); and 2048 columns of K = 64
+    ("gcn", (64, 2048, 256, 16), 140000, 500000, True, 2, "random"),
 ]
 
 
@@ -489,6 +492,8 @@ BF16_CASES = [
 @pytest.mark.parametrize("case", BF16_CASES, ids=lambda c: "%s-%s" % (c[0], "x".join(map(str, c[1]))))
 def test_bf16_storage_matches_oracle(case, order):
     model, dims, n, m_draw, sym, k, mode = case
+    if dims[1] == 2048 and order == "aggregate":
+        pytest.skip("the 2048-wide case takes half a minute per order: the other order covers the kernel")
     say("case bf16 %s layer order %s" % (case, order))
     from paper_2605_11517_amd import Session
     from synth import to_bf16_grid
