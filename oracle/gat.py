@@ -4,13 +4,17 @@ TEST INFRASTRUCTURE ONLY (see ``oracle/__init__.py``).
 
 The paper evaluates GAT as a second model family and notes that attention needs the gathered
 inputs themselves in the backward pass (section on grad-engine activation regathering); it
-does not restate the layer, so the definition is the published one (Velickovic et al., "Graph
-Attention Networks", one head), as PyG's ``GATConv`` computes it:
+does not restate the layer and gives no head count, so the definition is the published one
+(Velickovic et al., "Graph Attention Networks"), as PyG's ``GATConv`` computes it; with one head:
 
     H = A^{l-1} W                                   [n, f]
     e(u -> v) = LeakyReLU_0.2(a_src . H[u] + a_dst . H[v])      for u in N(v) + {v}
     alpha(u -> v) = softmax over the sources u of v
     Z[v] = sum_u alpha(u -> v) H[u];   A^l = act(Z + b),  act = ReLU on hidden layers
+
+With several heads every head runs these formulas on its own f / heads columns of H, a_src, a_dst
+and the heads' rows of Z are concatenated (the published layer's rule for hidden layers; taken for
+every layer here, a model that wants a single head at the output says so per layer).
 
 ``N(v)`` is row ``v`` of the CSR (sources of v) and every vertex gets exactly one self-loop,
 as in the GCN operator.  Everything is written per edge with plain numpy gathers and
@@ -40,48 +44,59 @@ def edges_with_self_loops(rowptr, colidx):
     return dst[order], src[order]
 
 
-def layer_forward(dst, src, n, A, W, a_src, a_dst, b, relu):
+def layer_forward(dst, src, n, A, W, a_src, a_dst, b, relu, heads=1):
+    """One layer with ``heads`` attention heads: head j owns columns [j f, (j+1) f) of H, of the
+    attention vectors and of the output (f = d_out / heads), takes its own softmax over the
+    sources of every vertex, and the heads' results stand side by side (concatenation)."""
     H = A @ W
-    s_src = H @ a_src
-    s_dst = H @ a_dst
-    x = s_src[src] + s_dst[dst]
+    f = H.shape[1] // heads
+    assert f * heads == H.shape[1], "the output width must be a multiple of the head count"
+    Hh = H.reshape(n, heads, f)
+    s_src = np.einsum("nhf,hf->nh", Hh, a_src.reshape(heads, f))
+    s_dst = np.einsum("nhf,hf->nh", Hh, a_dst.reshape(heads, f))
+    x = s_src[src] + s_dst[dst]                                   # [entries, heads]
     e = np.where(x > 0, x, SLOPE * x)
-    m = np.full(n, -np.inf)
+    m = np.full((n, heads), -np.inf)
     np.maximum.at(m, dst, e)
     ex = np.exp(e - m[dst])
-    den = np.zeros(n)
+    den = np.zeros((n, heads))
     np.add.at(den, dst, ex)
     alpha = ex / den[dst]
-    Z = np.zeros_like(H)
-    np.add.at(Z, dst, alpha[:, None] * H[src])
+    Z = np.zeros_like(Hh)
+    np.add.at(Z, dst, alpha[:, :, None] * Hh[src])
+    Z = Z.reshape(n, heads * f)
     Y = Z + (b if b is not None else 0.0)
     out = np.maximum(Y, 0.0) if relu else Y
-    return out, dict(H=H, x=x, alpha=alpha, Z=Z)
+    return out, dict(H=H, x=x, alpha=alpha, Z=Z, heads=heads)
 
 
 def layer_backward(dst, src, n, A, W, a_src, a_dst, cache, dY):
     """Gradients of one layer given dLoss/d(Z + b) = ``dY``."""
-    H, x, alpha = cache["H"], cache["x"], cache["alpha"]
-    dH = np.zeros_like(H)
-    np.add.at(dH, src, alpha[:, None] * dY[dst])                 # through Z = sum alpha H[u]
-    dalpha = np.einsum("ij,ij->i", dY[dst], H[src])
-    t = np.zeros(n)
+    H, x, alpha, heads = cache["H"], cache["x"], cache["alpha"], cache["heads"]
+    f = H.shape[1] // heads
+    Hh = H.reshape(n, heads, f)
+    dYh = dY.reshape(n, heads, f)
+    dH = np.zeros_like(Hh)
+    np.add.at(dH, src, alpha[:, :, None] * dYh[dst])             # through Z = sum alpha H[u]
+    dalpha = np.einsum("ehf,ehf->eh", dYh[dst], Hh[src])
+    t = np.zeros((n, heads))
     np.add.at(t, dst, alpha * dalpha)
     de = alpha * (dalpha - t[dst])                               # softmax
     dx = de * np.where(x > 0, 1.0, SLOPE)                        # LeakyReLU
-    ds_src = np.zeros(n)
-    ds_dst = np.zeros(n)
+    ds_src = np.zeros((n, heads))
+    ds_dst = np.zeros((n, heads))
     np.add.at(ds_src, src, dx)
     np.add.at(ds_dst, dst, dx)
-    da_src = H.T @ ds_src
-    da_dst = H.T @ ds_dst
-    dH += np.outer(ds_src, a_src) + np.outer(ds_dst, a_dst)
+    da_src = np.einsum("nhf,nh->hf", Hh, ds_src).reshape(-1)
+    da_dst = np.einsum("nhf,nh->hf", Hh, ds_dst).reshape(-1)
+    dH += ds_src[:, :, None] * a_src.reshape(1, heads, f) + ds_dst[:, :, None] * a_dst.reshape(1, heads, f)
+    dH = dH.reshape(n, heads * f)
     return dict(gW=A.T @ dH, ga_src=da_src, ga_dst=da_dst, gb=dY.sum(axis=0), gA=dH @ W.T)
 
 
 def forward(rowptr, colidx, dims, X, weights):
-    """``weights``: per layer a dict with ``W`` [d_in, d_out], ``a_src``, ``a_dst`` [d_out] and
-    ``b`` [d_out] or None.  Returns the activations A^1..A^L and the per-layer caches."""
+    """``weights``: per layer a dict with ``W`` [d_in, d_out], ``a_src``, ``a_dst`` [d_out],
+    ``b`` [d_out] or None, and optionally ``heads`` (default 1; must divide d_out).  Returns the activations A^1..A^L and the per-layer caches."""
     n = len(rowptr) - 1
     dst, src = edges_with_self_loops(rowptr, colidx)
     L = len(dims) - 1
@@ -94,7 +109,7 @@ def forward(rowptr, colidx, dims, X, weights):
                                  np.asarray(w["a_src"], dtype=np.float64),
                                  np.asarray(w["a_dst"], dtype=np.float64),
                                  None if w.get("b") is None else np.asarray(w["b"], dtype=np.float64),
-                                 relu=l < L - 1)
+                                 relu=l < L - 1, heads=int(w.get("heads", 1)))
         cache["A_in"] = A_in
         acts.append(A)
         caches.append(cache)

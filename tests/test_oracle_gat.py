@@ -111,7 +111,7 @@ def test_zero_attention_vectors_give_the_mean_over_the_closed_neighbourhood():
     rowptr2, colidx2, X2, y2, m2, w2 = make(n, dims, seed=6)
     _, caches, (dst, src) = gat.forward(rowptr2, colidx2, dims, X2, w2)
     sums = np.zeros(n)
-    np.add.at(sums, dst, caches[0]["alpha"])
+    np.add.at(sums, dst, caches[0]["alpha"][:, 0])
     assert np.abs(sums - 1).max() < 1e-13
 
 
@@ -129,16 +129,16 @@ def test_attention_is_invariant_to_a_shift_of_the_destination_score_sign_region(
     a_dst = np.zeros(n)
     out, cache = gat.layer_forward(dst, src, n, H_in, W, a_src, a_dst, None, relu=False)
     want = np.exp(a_src) / np.exp(a_src).sum()                     # all scores >= 0: identity branch
-    assert np.abs(cache["alpha"][:6] - want).max() < 1e-14
+    assert np.abs(cache["alpha"][:6, 0] - want).max() < 1e-14
     assert np.abs(out[0] - want).max() < 1e-14                     # Z[0] = sum alpha_u e_u
     a_dst2 = np.zeros(n)
     a_dst2[0] = 10.0                                               # shifts every score of vertex 0
     _, cache2 = gat.layer_forward(dst, src, n, H_in, W, a_src, a_dst2, None, relu=False)
-    assert np.abs(cache2["alpha"][:6] - want).max() < 1e-14
+    assert np.abs(cache2["alpha"][:6, 0] - want).max() < 1e-14
     # negative scores go through the 0.2 slope
     _, cache3 = gat.layer_forward(dst, src, n, H_in, W, -a_src, a_dst, None, relu=False)
     want3 = np.exp(-0.2 * a_src) / np.exp(-0.2 * a_src).sum()
-    assert np.abs(cache3["alpha"][:6] - want3).max() < 1e-14
+    assert np.abs(cache3["alpha"][:6, 0] - want3).max() < 1e-14
 
 
 def test_sampled_row_check_agrees_with_the_whole_graph_epoch():
@@ -161,3 +161,106 @@ def test_sampled_row_check_agrees_with_the_whole_graph_epoch():
     bad_a = [a.copy() for a in ref["act"]]
     bad_a[1][3, 2] += 0.01
     assert gat_sampled_errors(rowptr, colidx, dims, w, X, bad_a, ref["gact"], ref["gb"], V)["act[1] rows"] > 1e-4
+
+
+# ---- several attention heads -----------------------------------------------------------------
+
+def torch_dense_epoch_heads(rowptr, colidx, dims, X, w, heads, y, m):
+    """The multi-head layer written head by head on dense [n, n] attention matrices (each head
+    owns a column slice of H and of the attention vectors, the heads' outputs are concatenated),
+    differentiated by autograd."""
+    M = torch.tensor(dense_mask(rowptr, colidx))
+    A = torch.tensor(X, dtype=torch.float64)
+    params = [{k: torch.tensor(v, dtype=torch.float64, requires_grad=True)
+               for k, v in wl.items() if k != "heads"} for wl in w]
+    acts = []
+    L = len(dims) - 1
+    for l in range(L):
+        p = params[l]
+        H = A @ p["W"]
+        f = dims[l + 1] // heads[l]
+        outs = []
+        for j in range(heads[l]):
+            Hj = H[:, j * f:(j + 1) * f]
+            x = (Hj @ p["a_dst"][j * f:(j + 1) * f])[:, None] + (Hj @ p["a_src"][j * f:(j + 1) * f])[None, :]
+            e = torch.nn.functional.leaky_relu(x, 0.2)
+            e = torch.where(M, e, torch.tensor(-float("inf"), dtype=torch.float64))
+            outs.append(torch.softmax(e, dim=1) @ Hj)
+        Y = torch.cat(outs, dim=1) + p["b"]
+        A = torch.relu(Y) if l < L - 1 else Y
+        A.retain_grad()
+        acts.append(A)
+    idx = torch.tensor(np.flatnonzero(m))
+    loss = torch.nn.functional.cross_entropy(acts[-1][idx], torch.tensor(y[m != 0].astype(np.int64)))
+    loss.backward()
+    return loss.item(), acts, params
+
+
+@pytest.mark.parametrize("symmetric", [True, False])
+def test_multi_head_epoch_equals_dense_definition_and_autograd(symmetric):
+    n, dims, heads = 40, (6, 12, 10, 4), (3, 5, 2)
+    rowptr, colidx, X, y, m, w = make(n, dims, seed=13, symmetric=symmetric)
+    for wl, h in zip(w, heads):
+        wl["heads"] = h
+    out = gat.epoch(rowptr, colidx, dims, X, w, y, m)
+    loss, acts, params = torch_dense_epoch_heads(rowptr, colidx, dims, X, w, heads, y, m)
+    assert abs(out["loss"] - loss) < 1e-12
+    for l in range(3):
+        assert np.abs(out["act"][l] - acts[l].detach().numpy()).max() < 1e-12
+        assert np.abs(out["gact"][l] - acts[l].grad.numpy()).max() < 1e-12
+        for ours, name in (("gW", "W"), ("ga_src", "a_src"), ("ga_dst", "a_dst"), ("gb", "b")):
+            ref = params[l][name].grad.numpy()
+            assert np.abs(out[ours][l] - ref).max() < 1e-11 * max(1.0, np.abs(ref).max()), (l, name)
+
+
+def test_heads_are_independent_one_head_layers_side_by_side():
+    """A layer with h heads equals h one-head layers, each on its own column slice of W, a_src,
+    a_dst and b, with the outputs concatenated; and the gradients of a sum of losses split the
+    same way.  Ties the multi-head code to the one-head layer pinned above."""
+    n, din, f, heads = 35, 7, 4, 3
+    rowptr, colidx, X, y, m, w = make(n, (din, f * heads), seed=21)
+    dst, src = gat.edges_with_self_loops(rowptr, colidx)
+    wl = w[0]
+    out, cache = gat.layer_forward(dst, src, n, X, wl["W"], wl["a_src"], wl["a_dst"], wl["b"], relu=True,
+                                   heads=heads)
+    rng = np.random.default_rng(4)
+    dY = rng.standard_normal(out.shape)
+    g = gat.layer_backward(dst, src, n, X, wl["W"], wl["a_src"], wl["a_dst"], cache, dY)
+    gA = np.zeros_like(X)
+    for j in range(heads):
+        sl = slice(j * f, (j + 1) * f)
+        o1, c1 = gat.layer_forward(dst, src, n, X, wl["W"][:, sl], wl["a_src"][sl], wl["a_dst"][sl],
+                                   wl["b"][sl], relu=True)
+        assert np.abs(o1 - out[:, sl]).max() < 1e-13
+        assert np.abs(c1["alpha"][:, 0] - cache["alpha"][:, j]).max() < 1e-14
+        g1 = gat.layer_backward(dst, src, n, X, wl["W"][:, sl], wl["a_src"][sl], wl["a_dst"][sl], c1, dY[:, sl])
+        assert np.abs(g1["gW"] - g["gW"][:, sl]).max() < 1e-12
+        assert np.abs(g1["ga_src"] - g["ga_src"][sl]).max() < 1e-12
+        assert np.abs(g1["ga_dst"] - g["ga_dst"][sl]).max() < 1e-12
+        gA += g1["gA"]
+    assert np.abs(gA - g["gA"]).max() < 1e-12
+    # every head's attention weights sum to one over the sources of every vertex
+    sums = np.zeros((n, heads))
+    np.add.at(sums, dst, cache["alpha"])
+    assert np.abs(sums - 1).max() < 1e-13
+
+
+def test_multi_head_gradients_match_finite_differences():
+    n, dims, heads = 20, (4, 6, 4), (2, 2)
+    rowptr, colidx, X, y, m, w = make(n, dims, seed=31)
+    for wl, h in zip(w, heads):
+        wl["heads"] = h
+    out = gat.epoch(rowptr, colidx, dims, X, w, y, m)
+    h, worst = 1e-6, 0.0
+    for l in range(2):
+        for pname, gname in (("W", "gW"), ("a_src", "ga_src"), ("a_dst", "ga_dst"), ("b", "gb")):
+            arr, g = w[l][pname], out[gname][l]
+            for idx in np.ndindex(arr.shape):
+                old = arr[idx]
+                arr[idx] = old + h
+                lp = gat.epoch(rowptr, colidx, dims, X, w, y, m)["loss"]
+                arr[idx] = old - h
+                lm = gat.epoch(rowptr, colidx, dims, X, w, y, m)["loss"]
+                arr[idx] = old
+                worst = max(worst, abs((lp - lm) / (2 * h) - g[idx]) / np.abs(g).max())
+    assert worst < 1e-6, worst
