@@ -47,9 +47,10 @@ typedef enum {
     GNN_EUNSUPPORTED = 5  /* valid request this build does not implement */
 } gnn_status;
 
-/* GNN_GAT: graph-attention layers with one head (Velickovic et al.; the second model family of
- * the paper's evaluation): H = A^{l-1} W, e(u->v) = LeakyReLU_0.2(a_src.H[u] + a_dst.H[v]) over
- * the sources of v and v itself, softmax over the sources, A^l = act(sum alpha H[u] + b).
+/* GNN_GAT: graph-attention layers (Velickovic et al.; the second model family of the paper's
+ * evaluation): H = A^{l-1} W, e(u->v) = LeakyReLU_0.2(a_src.H[u] + a_dst.H[v]) over the sources
+ * of v and v itself, softmax over the sources, A^l = act(sum alpha H[u] + b).  One head per
+ * layer unless gnn_set_gat_heads says otherwise.
  * weights[3(l-1)+1] holds the two attention vectors as [2, d_l] (a_src, then a_dst), fp32.
  * GNN_F32 and the resident schedule only. */
 typedef enum { GNN_GCN = 0, GNN_SAGE_MEAN = 1, GNN_GAT = 2 } gnn_model;
@@ -357,6 +358,19 @@ gnn_status gnn_layer_is_transform_first(const gnn_ctx *ctx, int32_t layer, int32
  * GNN_ESTATE when the layer aggregates first or a sweep is incomplete. */
 gnn_status gnn_layer_transform_fwd(gnn_ctx *ctx, int32_t layer, int32_t p, void *stream);
 gnn_status gnn_layer_transform_bwd(gnn_ctx *ctx, int32_t layer, int32_t p, void *stream);
+
+/* Attention heads of one GNN_GAT layer (the paper's evaluation of graph attention names no head
+ * count; the layer is the published one, whose hidden layers concatenate their heads).  With
+ * `heads` = h the layer's d_l output columns are h groups of f = d_l / h: head j takes its own
+ * attention weights from columns [j f, (j + 1) f) of H = A^{l-1} W and of a_src, a_dst, aggregates
+ * those columns of H with them, and writes those columns of the output row (concatenation; the
+ * bias and the activation act on the whole row).  The shapes of W ([d_{l-1}, d_l]), of the
+ * attention vectors ([2, d_l]) and of every activation and gradient array stay as they are.
+ * The staged rows of such a layer are head-major (head j: |B_p| rows of f floats rounded up to
+ * whole 16-byte vectors).  Changes the workspace sizes: call before gnn_workspace_bytes /
+ * gnn_bind (a bound context becomes unbound).  GNN_EINVAL for another model, a layer outside
+ * 1..L, or a head count outside 1..64 or not dividing d_l. */
+gnn_status gnn_set_gat_heads(gnn_ctx *ctx, int32_t layer, int32_t heads);
 
 /* ---- training around the epoch (datasets table: learning rate, dropout, epochs) ---------- */
 

@@ -103,6 +103,7 @@ def load_library():
         "gnn_layer_bwd": [vp, i32, i32, vp],
         "gnn_epoch": [vp, vp, P(C.c_float)],
         "gnn_set_layer_order": [vp, i32],
+        "gnn_set_gat_heads": [vp, i32, i32],
         "gnn_layer_is_transform_first": [vp, i32, P(i32)],
         "gnn_layer_transform_fwd": [vp, i32, i32, vp],
         "gnn_layer_transform_bwd": [vp, i32, i32, vp],
@@ -290,6 +291,9 @@ class Context:
     def set_layer_order(self, mode):
         self._check(self.lib.gnn_set_layer_order(self.h, {"aggregate": 0, "auto": 1}[mode]))
 
+    def set_gat_heads(self, layer, heads):
+        self._check(self.lib.gnn_set_gat_heads(self.h, int(layer), int(heads)))
+
     def layer_is_transform_first(self, layer):
         out = C.c_int32()
         self._check(self.lib.gnn_layer_is_transform_first(self.h, layer, C.byref(out)))
@@ -387,6 +391,11 @@ class Session:
         self.ctx.set_layer_order(layer_order)
         self.ctx.set_gather_fusion(fuse_gather)
         self.ctx.set_masked_backward(masked_backward)
+        if _MODEL.get(model, model) == GNN_GAT:
+            # attention heads per layer: weights[l]["heads"] (default 1)
+            for l, wl in enumerate(weights):
+                if int(wl.get("heads", 1)) != 1:
+                    self.ctx.set_gat_heads(l + 1, int(wl["heads"]))
         say = progress or (lambda msg: None)
         self.ctx.build_partitions(rowptr, colidx, k, part_mode, seed, user_part)
         say("partitions built")

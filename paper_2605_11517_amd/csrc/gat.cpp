@@ -1,4 +1,5 @@
-// Graph-attention layers on partitions (one head; the layer definition is Velickovic et al.'s,
+// Graph-attention layers on partitions (one or several heads, the heads' outputs side by side;
+// the layer definition is Velickovic et al.'s,
 // the model family the paper evaluates next to GCN and GraphSAGE; its section on activation
 // regathering notes that attention needs the gathered inputs themselves in the backward pass).
 //
@@ -17,36 +18,45 @@ namespace gnnmi {
 
 namespace {
 
+// One head of a layer on one partition.  With one head: f = d_l, fp = the padded row width, and
+// every offset below is zero.  With several, head j is a layer of its own on columns
+// [j f, (j + 1) f) of W, of the attention vectors, of the bias and of the output, with its own
+// arrays of H, grad H (fp floats per vertex) and scores (one float per vertex).
 struct GatView {
-    int64_t r0, np, nb, e0;
-    int32_t din, dout, dp;
-    float *H, *gH, *ssrc, *sdst, *gssrc, *gsdst, *bs, *att, *dal, *twatt;
-    const float *a_src, *a_dst;
+    int64_t r0, np, nb, e0, n;
+    int32_t din, dout, nh, f, fp;
+    float *H, *gH, *ssrc, *sdst, *gssrc, *gsdst, *bs, *att, *dal, *twatt, *stg;
+    const float *W, *a_src, *a_dst;
 };
 
-GatView view(gnn_ctx* c, int32_t layer, int32_t p)
+GatView view(gnn_ctx* c, int32_t layer, int32_t p, int32_t h)
 {
     const HostMeta& M = c->M;
     GatView v;
+    v.n = M.n;
     v.r0 = M.off[(size_t)p];
     v.np = M.off[(size_t)p + 1] - v.r0;
     v.nb = M.boff[(size_t)p + 1] - M.boff[(size_t)p];
     v.e0 = M.rp[(size_t)v.r0];
     v.din = c->dims[(size_t)layer - 1];
     v.dout = c->dims[(size_t)layer];
-    v.dp = c->padded(layer);
+    v.nh = c->nheads(layer);
+    v.f = c->head_cols(layer);
+    v.fp = c->head_padded(layer);
     char* sc = c->scratch;
-    v.H = (float*)c->hbuf;
-    v.gH = (float*)c->ghbuf;
-    v.ssrc = (float*)(sc + c->ws.ssrc);
-    v.sdst = (float*)(sc + c->ws.sdst);
-    v.gssrc = (float*)(sc + c->ws.gssrc);
-    v.gsdst = (float*)(sc + c->ws.gsdst);
-    v.bs = (float*)(sc + c->ws.bs);
+    v.H = (float*)c->hbuf + (int64_t)h * v.n * v.fp;
+    v.gH = (float*)c->ghbuf + (int64_t)h * v.n * v.fp;
+    v.ssrc = (float*)(sc + c->ws.ssrc) + (int64_t)h * v.n;
+    v.sdst = (float*)(sc + c->ws.sdst) + (int64_t)h * v.n;
+    v.gssrc = (float*)(sc + c->ws.gssrc) + (int64_t)h * v.n;
+    v.gsdst = (float*)(sc + c->ws.gsdst) + (int64_t)h * v.n;
+    v.bs = (float*)(sc + c->ws.bs) + (int64_t)h * v.nb;
+    v.stg = (float*)c->staging + (int64_t)h * v.nb * v.fp;
     v.att = (float*)(sc + c->ws.att);
     v.dal = (float*)(sc + c->ws.dal);
     v.twatt = (float*)(sc + c->ws.twatt);
-    v.a_src = (const float*)c->w[(size_t)3 * (layer - 1) + 1];
+    v.W = (const float*)c->w[(size_t)3 * (layer - 1)] + (int64_t)h * v.f;
+    v.a_src = (const float*)c->w[(size_t)3 * (layer - 1) + 1] + (int64_t)h * v.f;
     v.a_dst = v.a_src + v.dout;
     return v;
 }
@@ -69,153 +79,192 @@ GatRowsHost rows_of(gnn_ctx* c, const GatView& v, int32_t p)
 
 void gat_transform_fwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
 {
-    const GatView v = view(c, layer, p);
-    float* Hp = v.H + v.r0 * v.dp;
-    if (v.dp != v.dout) {
+    const int32_t nh = c->nheads(layer);
+    for (int32_t h = 0; h < nh; ++h) {
+        const GatView v = view(c, layer, p, h);
+        float* Hp = v.H + v.r0 * v.fp;
+        if (v.fp != v.f) {
+            Timed t(c, s, GNN_K_OTHER);
+            launch_fill_zero(Hp, v.np * (int64_t)v.fp * 4, s);
+        }
+        {
+            Timed t(c, s, GNN_K_GEMM_FWD);
+            GemmSeg seg;
+            seg.a = (const float*)c->layer_input(layer, v.r0); seg.lda = v.din;
+            seg.b = v.W; seg.ldb = v.dout; seg.k = v.din;
+            launch_gemm_nn(&seg, 1, Hp, v.fp, v.np, v.f, GemmEpilogue{}, s);
+        }
         Timed t(c, s, GNN_K_OTHER);
-        launch_fill_zero(Hp, v.np * (int64_t)v.dp * 4, s);
+        launch_gat_scores(Hp, v.fp, v.f, v.np, v.a_src, v.a_dst, v.ssrc + v.r0, v.sdst + v.r0, s);
     }
-    {
-        Timed t(c, s, GNN_K_GEMM_FWD);
-        GemmSeg seg;
-        seg.a = (const float*)c->layer_input(layer, v.r0); seg.lda = v.din;
-        seg.b = (const float*)c->w[(size_t)3 * (layer - 1)]; seg.ldb = v.dout; seg.k = v.din;
-        launch_gemm_nn(&seg, 1, Hp, v.dp, v.np, v.dout, GemmEpilogue{}, s);
-    }
-    Timed t(c, s, GNN_K_OTHER);
-    launch_gat_scores(Hp, v.dp, v.dout, v.np, v.a_src, v.a_dst, v.ssrc + v.r0, v.sdst + v.r0, s);
 }
 
-// rows of H and scores s_src of the boundary vertices of p
+// rows of H and scores s_src of the boundary vertices of p, head by head
 void gat_gather(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
 {
-    const GatView v = view(c, layer, p);
+    const int32_t nh = c->nheads(layer);
     const int32_t* bnd = c->D.bnd + c->M.boff[(size_t)p];
     Timed t(c, s, GNN_K_GATHER);
-    launch_gather_rows(v.H, bnd, c->staging, v.nb, (int64_t)v.dp * 4, s);
-    launch_gather_rows(v.ssrc, bnd, v.bs, v.nb, 4, s);
+    for (int32_t h = 0; h < nh; ++h) {
+        const GatView v = view(c, layer, p, h);
+        launch_gather_rows(v.H, bnd, v.stg, v.nb, (int64_t)v.fp * 4, s);
+        launch_gather_rows(v.ssrc, bnd, v.bs, v.nb, 4, s);
+    }
 }
 
 void gat_layer_fwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
 {
-    const GatView v = view(c, layer, p);
-    const GatRowsHost rows = rows_of(c, v, p);
-    {
-        Timed t(c, s, GNN_K_OTHER);
-        launch_gat_attention(rows, v.att, (float*)(c->scratch + c->ws.segpart), s);
-    }
+    const int32_t nh = c->nheads(layer);
     float* Z = (float*)(c->scratch + c->ws.z);
     float* segpart = (float*)(c->scratch + c->ws.segpart);
-    {
-        Timed t(c, s, GNN_K_SPMM);
-        launch_spmm(rows.rp, rows.col, v.att - v.e0, nullptr, v.H + v.r0 * v.dp, v.np, c->staging, Z, v.np, v.dp,
-                    0, 0, rows.items, segpart, 1, SpmmScatter{}, s);
+    for (int32_t h = 0; h < nh; ++h) {
+        const GatView v = view(c, layer, p, h);
+        const GatRowsHost rows = rows_of(c, v, p);
+        {
+            Timed t(c, s, GNN_K_OTHER);
+            launch_gat_attention(rows, v.att, segpart, s);
+        }
+        {
+            Timed t(c, s, GNN_K_SPMM);
+            launch_spmm(rows.rp, rows.col, v.att - v.e0, nullptr, v.H + v.r0 * v.fp, v.np, v.stg, Z, v.np, v.fp,
+                        0, 0, rows.items, segpart, 1, SpmmScatter{}, s);
+        }
+        if (rows.items.nlong > 0) {
+            Timed t(c, s, GNN_K_SPMM_REDUCE);
+            launch_spmm_reduce(nullptr, Z, v.fp, 0, rows.items, segpart, SpmmScatter{}, s);
+        }
+        // the head's columns of the output rows
+        float* out = (float*)c->act[(size_t)layer - 1] + v.r0 * v.dout + (int64_t)h * v.f;
+        const float* bias = c->has_bias ? (const float*)c->w[(size_t)3 * (layer - 1) + 2] + (int64_t)h * v.f : nullptr;
+        Timed t(c, s, GNN_K_GEMM_FWD);
+        launch_add_padded(out, Z, v.np, v.f, v.fp, bias, 0, layer < c->L ? 1 : 0, s, v.dout);
     }
-    if (rows.items.nlong > 0) {
-        Timed t(c, s, GNN_K_SPMM_REDUCE);
-        launch_spmm_reduce(nullptr, Z, v.dp, 0, rows.items, segpart, SpmmScatter{}, s);
-    }
-    float* out = (float*)c->act[(size_t)layer - 1] + v.r0 * v.dout;
-    const float* bias = c->has_bias ? (const float*)c->w[(size_t)3 * (layer - 1) + 2] : nullptr;
-    Timed t(c, s, GNN_K_GEMM_FWD);
-    launch_add_padded(out, Z, v.np, v.dout, v.dp, bias, 0, layer < c->L ? 1 : 0, s);
 }
 
 // first partition of a layer's backward pass: the accumulators start from zero
 void gat_bwd_begin(gnn_ctx* c, int32_t layer, hipStream_t s)
 {
     const int64_t n = c->M.n;
+    const int64_t nh = c->nheads(layer);
     Timed t(c, s, GNN_K_OTHER);
-    launch_fill_zero(c->ghbuf, n * (int64_t)c->padded(layer) * 4, s);
-    launch_fill_zero(c->scratch + c->ws.gssrc, n * 4, s);
-    launch_fill_zero(c->scratch + c->ws.gsdst, n * 4, s);
+    launch_fill_zero(c->ghbuf, n * (int64_t)c->hrow(layer) * 4, s);
+    launch_fill_zero(c->scratch + c->ws.gssrc, n * nh * 4, s);
+    launch_fill_zero(c->scratch + c->ws.gsdst, n * nh * 4, s);
     // grad A^{l-1} needs no initialisation: each of its rows is written once, by grad H_p W^T
 }
 
 void gat_layer_bwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
 {
     const HostMeta& M = c->M;
-    const GatView v = view(c, layer, p);
-    const GatRowsHost rows = rows_of(c, v, p);
+    const int32_t nh = c->nheads(layer);
+    const GatView v0 = view(c, layer, p, 0);
     float* gb = c->has_bias ? c->gw[(size_t)3 * (layer - 1) + 2] : nullptr;
     float* dYbuf = (float*)(c->scratch + c->ws.dy);
     float* colpart = (float*)(c->scratch + c->ws.colpart);
-    const float* g_own = c->gact[(size_t)layer - 1] + v.r0 * v.dout;
+    const float* g_own = c->gact[(size_t)layer - 1] + v0.r0 * v0.dout;
     const float* dY = g_own;
     {
         Timed t(c, s, GNN_K_ACT_BWD);
         if (layer < c->L) {
-            launch_act_bwd(g_own, (const float*)c->act[(size_t)layer - 1] + v.r0 * v.dout, dYbuf, v.np, v.dout, gb,
+            launch_act_bwd(g_own, (const float*)c->act[(size_t)layer - 1] + v0.r0 * v0.dout, dYbuf, v0.np, v0.dout, gb,
                            colpart, 1.f, s);
             dY = dYbuf;
         } else {
-            launch_act_bwd(g_own, nullptr, nullptr, v.np, v.dout, gb, colpart, 1.f, s);
+            launch_act_bwd(g_own, nullptr, nullptr, v0.np, v0.dout, gb, colpart, 1.f, s);
         }
-    }
-    const float* dYp = dY;
-    if (v.dp != v.dout) {
-        Timed t(c, s, GNN_K_OTHER);
-        float* pad = (float*)(c->scratch + c->ws.dz);
-        launch_pad_rows(pad, dY, v.np, v.dout, v.dp, s);
-        dYp = pad;
-    }
-    {
-        // recompute the attention weights from the regathered scores
-        Timed t(c, s, GNN_K_OTHER);
-        launch_gat_attention(rows, v.att, (float*)(c->scratch + c->ws.segpart), s);
-    }
-    {
-        Timed t(c, s, GNN_K_SPMM);      // edge-wise products: one source row read per entry
-        launch_gat_dots(rows.rp, rows.col, v.e0, v.np, v.H + v.r0 * v.dp, (const float*)c->staging, dYp, v.dp,
-                        v.dal, rows.items, s);
     }
     const int64_t t0 = M.toff[(size_t)p];
     const SpmmItems titems = plan_items(M.plan_bwd, c->D.bwd, p);
     const int32_t* bnd = c->D.bnd + M.boff[(size_t)p];
-    {
-        Timed t(c, s, GNN_K_OTHER);
-        launch_gat_bwd_scalars(rows, v.att, v.dal, v.gsdst + v.r0, (float*)(c->scratch + c->ws.segpart), s);
-        launch_gat_transposed(c->D.trp + t0, c->D.tperm, v.e0, v.np, v.r0, bnd, titems, v.att, v.dal, v.twatt,
-                              v.gssrc, s);
-    }
     float* segpart = (float*)(c->scratch + c->ws.segpart);
-    SpmmScatter sc;
-    sc.n_own = v.np;
-    sc.base_row = v.r0;
-    sc.idx = bnd;
-    {
-        Timed t(c, s, GNN_K_SPMM_T);
-        launch_spmm(c->D.trp + t0, c->D.tcol, v.twatt - v.e0, nullptr, dYp, v.np, nullptr, v.gH, v.np + v.nb, v.dp,
-                    0, 0, titems, segpart, 0, sc, s);
-    }
-    if (titems.nlong > 0) {
-        Timed t(c, s, GNN_K_SPMM_REDUCE);
-        launch_spmm_reduce(nullptr, v.gH, v.dp, 0, titems, segpart, sc, s);
+    for (int32_t h = 0; h < nh; ++h) {
+        const GatView v = view(c, layer, p, h);
+        const GatRowsHost rows = rows_of(c, v, p);
+        // the head's columns of dY as rows of fp floats
+        const float* dYp = dY;
+        if (nh > 1 || v.fp != v.f) {
+            Timed t(c, s, GNN_K_OTHER);
+            float* pad = (float*)(c->scratch + c->ws.dz);
+            launch_pad_rows(pad, dY + (int64_t)h * v.f, v.np, v.f, v.fp, s, v.dout);
+            dYp = pad;
+        }
+        {
+            // recompute the attention weights from the regathered scores
+            Timed t(c, s, GNN_K_OTHER);
+            launch_gat_attention(rows, v.att, segpart, s);
+        }
+        {
+            Timed t(c, s, GNN_K_SPMM);      // edge-wise products: one source row read per entry
+            launch_gat_dots(rows.rp, rows.col, v.e0, v.np, v.H + v.r0 * v.fp, v.stg, dYp, v.fp, v.dal, rows.items, s);
+        }
+        {
+            Timed t(c, s, GNN_K_OTHER);
+            launch_gat_bwd_scalars(rows, v.att, v.dal, v.gsdst + v.r0, segpart, s);
+            launch_gat_transposed(c->D.trp + t0, c->D.tperm, v.e0, v.np, v.r0, bnd, titems, v.att, v.dal, v.twatt,
+                                  v.gssrc, s);
+        }
+        SpmmScatter sc;
+        sc.n_own = v.np;
+        sc.base_row = v.r0;
+        sc.idx = bnd;
+        {
+            Timed t(c, s, GNN_K_SPMM_T);
+            launch_spmm(c->D.trp + t0, c->D.tcol, v.twatt - v.e0, nullptr, dYp, v.np, nullptr, v.gH, v.np + v.nb, v.fp,
+                        0, 0, titems, segpart, 0, sc, s);
+        }
+        if (titems.nlong > 0) {
+            Timed t(c, s, GNN_K_SPMM_REDUCE);
+            launch_spmm_reduce(nullptr, v.gH, v.fp, 0, titems, segpart, sc, s);
+        }
     }
 }
 
 void gat_transform_bwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
 {
-    const GatView v = view(c, layer, p);
-    float* gHp = v.gH + v.r0 * v.dp;
-    const float* Hp = v.H + v.r0 * v.dp;
+    const int32_t nh = c->nheads(layer);
     float* part = (float*)(c->scratch + c->ws.colpart);
-    {
-        Timed t(c, s, GNN_K_OTHER);
-        launch_gat_rank1(gHp, Hp, v.dp, v.dout, v.np, v.gssrc + v.r0, v.gsdst + v.r0, v.a_src, v.a_dst, part, s);
-        launch_colsum_finish(part, (v.np + 255) / 256, 2 * v.dout, c->gw[(size_t)3 * (layer - 1) + 1], s);
-    }
-    const float* in_own = (const float*)c->layer_input(layer, v.r0);
-    {
+    float* ga = c->gw[(size_t)3 * (layer - 1) + 1];       // grad a_src (d_l floats), then grad a_dst
+    for (int32_t h = 0; h < nh; ++h) {
+        const GatView v = view(c, layer, p, h);
+        float* gHp = v.gH + v.r0 * v.fp;
+        const float* Hp = v.H + v.r0 * v.fp;
+        {
+            Timed t(c, s, GNN_K_OTHER);
+            launch_gat_rank1(gHp, Hp, v.fp, v.f, v.np, v.gssrc + v.r0, v.gsdst + v.r0, v.a_src, v.a_dst, part, s);
+            if (nh == 1) {
+                launch_colsum_finish(part, (v.np + 255) / 256, 2 * v.dout, ga, s);
+            } else {
+                launch_colsum_finish(part, (v.np + 255) / 256, v.f, ga + (int64_t)h * v.f, s, 2 * v.f);
+                launch_colsum_finish(part + v.f, (v.np + 255) / 256, v.f, ga + v.dout + (int64_t)h * v.f, s, 2 * v.f);
+            }
+        }
+        const float* in_own = (const float*)c->layer_input(layer, v.r0);
         Timed t(c, s, GNN_K_GEMM_DW);
-        launch_gemm_tn(in_own, v.din, gHp, v.dp, c->gw[(size_t)3 * (layer - 1)], v.dout, v.din, v.dout, v.np,
-                       (float*)(c->scratch + c->ws.partial), s);
+        launch_gemm_tn(in_own, v.din, gHp, v.fp, c->gw[(size_t)3 * (layer - 1)] + (int64_t)h * v.f, v.dout, v.din,
+                       v.f, v.np, (float*)(c->scratch + c->ws.partial), s);
     }
     if (layer >= 2) {
+        // grad A^{l-1}_p = sum over heads of grad H_p W^T on the head's columns: written by the
+        // first contraction (two heads at a time), accumulated by the others
         Timed t(c, s, GNN_K_GEMM_DZ);
-        GemmEpilogue ep;                 // the only term of grad A^{l-1}_p: written, not accumulated
-        launch_gemm_nt(gHp, v.dp, (const float*)c->w[(size_t)3 * (layer - 1)], v.dout,
-                       c->gact[(size_t)layer - 2] + v.r0 * v.din, v.din, v.np, v.din, v.dout, ep, s);
+        const GatView v = view(c, layer, p, 0);
+        float* out = c->gact[(size_t)layer - 2] + v.r0 * v.din;
+        if (nh == 1) {
+            launch_gemm_nt(v.gH + v.r0 * v.fp, v.fp, v.W, v.dout, out, v.din, v.np, v.din, v.dout, GemmEpilogue{}, s);
+        } else {
+            for (int32_t h0 = 0; h0 < nh; h0 += 2) {
+                GemmSeg segs[2];
+                const int nseg = nh - h0 < 2 ? 1 : 2;
+                for (int i = 0; i < nseg; ++i) {
+                    const GatView vh = view(c, layer, p, h0 + i);
+                    segs[i].a = vh.gH + vh.r0 * vh.fp; segs[i].lda = vh.fp;
+                    segs[i].b = vh.W; segs[i].ldb = vh.dout; segs[i].k = vh.f;
+                }
+                GemmEpilogue ep;
+                ep.accumulate = h0 > 0 ? 1 : 0;
+                launch_gemm_nt2(segs, nseg, out, v.din, v.np, v.din, ep, s);
+            }
+        }
     }
 }
 

@@ -267,6 +267,10 @@ void compute_workspace(gnn_ctx* c)
         dout = std::max<int64_t>(dout, c->dims[(size_t)l + 1]);
         int sp = gemm_tn_splits(max_np, c->dims[(size_t)l], c->dims[(size_t)l + 1]);
         part = std::max(part, (int64_t)sp * c->dims[(size_t)l] * c->dims[(size_t)l + 1]);
+        if (c->nheads(l + 1) > 1) {   // the weight gradient is taken head by head
+            sp = gemm_tn_splits(max_np, c->dims[(size_t)l], c->head_cols(l + 1));
+            part = std::max(part, (int64_t)sp * c->dims[(size_t)l] * c->head_cols(l + 1));
+        }
         if (c->bf16())
             part = std::max(part, gemm_bf16_tn_partial_floats(max_np, c->dims[(size_t)l], c->dims[(size_t)l + 1]));
     }
@@ -274,7 +278,7 @@ void compute_workspace(gnn_ctx* c)
     // wide as the widest aggregated row: an input width, or the padded output width of a layer
     // that transforms first
     for (int32_t l = 1; l <= L; ++l)
-        if (c->transform_first(l)) din = std::max<int64_t>(din, c->padded(l));
+        if (c->transform_first(l)) din = std::max<int64_t>(din, c->hrow(l));
     Workspace& w = c->ws;
     w.staging_bytes = align_up(std::max<int64_t>(1, max_b * din * 4));
     int64_t o = 0;
@@ -299,7 +303,7 @@ void compute_workspace(gnn_ctx* c)
     }
     int64_t hp = 0;
     for (int32_t l = 1; l <= L; ++l)
-        if (c->transform_first(l)) hp = std::max<int64_t>(hp, c->padded(l));
+        if (c->transform_first(l)) hp = std::max<int64_t>(hp, c->hrow(l));
     w.h = w.gh = 0;
     w.h_floats = w.dyall_floats = 0;
     if (hp > 0) {
@@ -325,11 +329,12 @@ void compute_workspace(gnn_ctx* c)
         }
     }
     if (c->model == GNN_GAT) {
-        w.ssrc = take(M.n);
-        w.sdst = take(M.n);
-        w.gssrc = take(M.n);
-        w.gsdst = take(M.n);
-        w.bs = take(max_b);
+        const int64_t mh = c->max_heads();      // per-vertex scores: one array of n floats per head
+        w.ssrc = take(M.n * mh);
+        w.sdst = take(M.n * mh);
+        w.gssrc = take(M.n * mh);
+        w.gsdst = take(M.n * mh);
+        w.bs = take(max_b * mh);
         w.att = take(M.stats.max_nnz);
         w.dal = take(M.stats.max_nnz);
         w.twatt = take(M.stats.max_nnz);
@@ -1375,6 +1380,21 @@ gnn_status gnn_set_layer_order(gnn_ctx* c, int32_t mode)
         return c->fail(GNN_EINVAL, "unknown layer order");
     c->order_mode = mode;
     c->bound = false;              // workspace sizes depend on the order
+    if (c->built) compute_workspace(c);
+    return GNN_OK;
+}
+
+gnn_status gnn_set_gat_heads(gnn_ctx* c, int32_t layer, int32_t heads)
+{
+    if (!c) return GNN_EINVAL;
+    if (c->model != GNN_GAT) return c->fail(GNN_EINVAL, "attention heads exist for GNN_GAT only");
+    if (layer < 1 || layer > c->L) return c->fail(GNN_EINVAL, "layer outside 1..L");
+    if (heads < 1 || heads > 64 || c->dims[(size_t)layer] % heads != 0)
+        return c->fail(GNN_EINVAL, "the head count must be in 1..64 and divide the layer's output width");
+    if (c->heads.empty()) c->heads.assign((size_t)c->L, 1);
+    c->heads[(size_t)layer - 1] = heads;
+    c->bound = false;              // workspace sizes depend on the head counts
+    c->h_layer = 0;
     if (c->built) compute_workspace(c);
     return GNN_OK;
 }

@@ -162,6 +162,22 @@ struct gnn_ctx {
     }
     // width of H rows: d_layer rounded up to whole 16-byte vectors
     int32_t padded(int32_t layer) const { return (dims[(size_t)layer] + 3) / 4 * 4; }
+    // graph attention: heads of layer l at [l - 1] (empty: one head everywhere).  With several
+    // heads H, grad H and the staged rows are kept head by head: head j of a layer is an array
+    // of its own with head_padded(l) floats per vertex (its f = d_l / heads columns rounded up to
+    // whole 16-byte vectors), the heads one after the other.
+    std::vector<int32_t> heads;
+    int32_t nheads(int32_t layer) const { return heads.empty() ? 1 : heads[(size_t)layer - 1]; }
+    int32_t head_cols(int32_t layer) const { return dims[(size_t)layer] / nheads(layer); }
+    int32_t head_padded(int32_t layer) const { return (head_cols(layer) + 3) / 4 * 4; }
+    // floats of H per vertex over all heads (= padded(layer) with one head)
+    int32_t hrow(int32_t layer) const { return nheads(layer) * head_padded(layer); }
+    int32_t max_heads() const
+    {
+        int32_t m = 1;
+        for (int32_t h : heads) m = std::max(m, h);
+        return m;
+    }
     std::vector<uint8_t> xf_fwd_done, xf_bwd_done;   // L * k: transform sweeps of such layers
     int32_t h_layer = 0;                             // layer whose H = A W the scratch buffer holds
     // schedule state

@@ -305,17 +305,20 @@ void launch_gat_transposed(const int64_t* trp, const int32_t* tperm, int64_t e0,
 int64_t gat_rank1_partial_floats(int64_t rows, int32_t f);
 void launch_gat_rank1(float* gH, const float* H, int32_t ld, int32_t f, int64_t rows, const float* gs_src,
                       const float* gs_dst, const float* a_src, const float* a_dst, float* partial, hipStream_t s);
-// out[c] += sum over b < nblocks of partial[b * d + c]
-void launch_colsum_finish(const float* partial, int64_t nblocks, int32_t d, float* out, hipStream_t s);
+// out[c] += sum over b < nblocks of partial[b * ldp + c] for c < d (ldp = 0: rows of d floats)
+void launch_colsum_finish(const float* partial, int64_t nblocks, int32_t d, float* out, hipStream_t s,
+                          int32_t ldp = 0);
 
 // Transform-first layers: out = (accumulate ? out : 0) + z[:, :d] (+ bias), optional relu, with
-// z's row stride ldz >= d; and a row copy into a wider, zero-padded row.
+// z's row stride ldz >= d and out's row stride ldo (0: d); and a row copy into a wider,
+// zero-padded row (source rows lds floats apart, 0: d).
 void launch_add_padded(float* out, const float* z, int64_t rows, int32_t d, int32_t ldz,
-                       const float* bias, int accumulate, int relu, hipStream_t s);
+                       const float* bias, int accumulate, int relu, hipStream_t s, int32_t ldo = 0);
 // out[i, :] = bfloat16(act(z[i, 0..d) + bias)), z fp32 with row stride ldz
 void launch_bias_act_bf16(void* out, const float* z, int64_t rows, int32_t d, int32_t ldz, const float* bias,
                           int relu, hipStream_t s);
-void launch_pad_rows(float* dst, const float* src, int64_t rows, int32_t d, int32_t ld, hipStream_t s);
+void launch_pad_rows(float* dst, const float* src, int64_t rows, int32_t d, int32_t ld, hipStream_t s,
+                     int32_t lds = 0);
 
 // Training pieces: dropout on a block of activation rows (orig_of_row[r] = original vertex id
 // of row r), and the optimizer steps on one fp32 parameter tensor.

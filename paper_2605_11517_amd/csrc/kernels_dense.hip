@@ -380,7 +380,7 @@ __global__ __launch_bounds__(kBlock) void k_act_bwd_bf16_vec(const float* __rest
 constexpr int kFinishGroups = 32;
 __global__ __launch_bounds__(32 * kFinishGroups) void k_colsum_finish(const float* __restrict__ partial,
                                                                       int64_t nblocks, int32_t d,
-                                                                      float* __restrict__ gb)
+                                                                      float* __restrict__ gb, int32_t ldp)
 {
     __shared__ float sm[kFinishGroups][32];
     const int tx = threadIdx.x % 32, ty = threadIdx.x / 32;
@@ -392,7 +392,7 @@ __global__ __launch_bounds__(32 * kFinishGroups) void k_colsum_finish(const floa
             float x[U];
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                x[u] = b + kFinishGroups * u < nblocks ? partial[(b + kFinishGroups * u) * d + c] : 0.f;
+                x[u] = b + kFinishGroups * u < nblocks ? partial[(b + kFinishGroups * u) * ldp + c] : 0.f;
 #pragma unroll
             for (int u = 0; u < U; ++u) s += x[u];
         }
@@ -445,7 +445,7 @@ __global__ __launch_bounds__(kBlock) void k_dropout(T* __restrict__ a, const int
 __global__ __launch_bounds__(kBlock) void k_add_padded(float* __restrict__ out, const float* __restrict__ z,
                                                        int64_t rows, int32_t d, int32_t ldz,
                                                        const float* __restrict__ bias, int accumulate,
-                                                       int relu)
+                                                       int relu, int32_t ldo)
 {
     const int64_t total = rows * d;
     for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < total;
@@ -453,10 +453,10 @@ __global__ __launch_bounds__(kBlock) void k_add_padded(float* __restrict__ out, 
         const int64_t r = i / d;
         const int32_t j = (int32_t)(i - r * d);
         float v = z[r * ldz + j];
-        if (accumulate) v += out[i];
+        if (accumulate) v += out[r * ldo + j];
         if (bias) v += bias[j];
         if (relu) v = v > 0.f ? v : 0.f;
-        out[i] = v;
+        out[r * ldo + j] = v;
     }
 }
 
@@ -506,14 +506,14 @@ __global__ __launch_bounds__(kBlock) void k_bias_act_bf16_vec(uint4* __restrict_
 
 // dst[r, 0..ld) = src[r, 0..d) followed by zeros (ld >= d)
 __global__ __launch_bounds__(kBlock) void k_pad_rows(float* __restrict__ dst, const float* __restrict__ src,
-                                                     int64_t rows, int32_t d, int32_t ld)
+                                                     int64_t rows, int32_t d, int32_t ld, int32_t lds)
 {
     const int64_t total = rows * ld;
     for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < total;
          i += (int64_t)gridDim.x * kBlock) {
         const int64_t r = i / ld;
         const int32_t j = (int32_t)(i - r * ld);
-        dst[i] = j < d ? src[r * d + j] : 0.f;
+        dst[i] = j < d ? src[r * lds + j] : 0.f;
     }
 }
 
@@ -666,7 +666,7 @@ void launch_act_bwd(const float* g, const float* act, float* dy, int64_t rows, i
                            partial, scale, row_on);
     if (gb)
         hipLaunchKernelGGL(k_colsum_finish, dim3((unsigned)((d + 31) / 32)), dim3(32 * kFinishGroups),
-                           0, s, (const float*)partial, blocks, d, gb);
+                           0, s, (const float*)partial, blocks, d, gb, d);
 }
 
 void launch_act_bwd_bf16(const float* g, const void* act, void* dy, int64_t rows, int32_t d,
@@ -686,7 +686,7 @@ void launch_act_bwd_bf16(const float* g, const void* act, void* dy, int64_t rows
                            (const uint16_t*)act, (uint16_t*)dy, rows, d, partial, scale);
     if (gb)
         hipLaunchKernelGGL(k_colsum_finish, dim3((unsigned)((d + 31) / 32)), dim3(32 * kFinishGroups), 0, s,
-                           (const float*)partial, blocks, d, gb);
+                           (const float*)partial, blocks, d, gb, d);
 }
 
 void launch_dropout(void* a, int is_bf16, const int32_t* orig_of_row, int64_t rows, int32_t d,
@@ -703,21 +703,21 @@ void launch_dropout(void* a, int is_bf16, const int32_t* orig_of_row, int64_t ro
                            orig_of_row, rows, d, (unsigned long long)key, threshold, scale);
 }
 
-void launch_colsum_finish(const float* partial, int64_t nblocks, int32_t d, float* out, hipStream_t s)
+void launch_colsum_finish(const float* partial, int64_t nblocks, int32_t d, float* out, hipStream_t s, int32_t ldp)
 {
     if (nblocks <= 0 || d <= 0) return;
     hipLaunchKernelGGL(k_colsum_finish, dim3((unsigned)((d + 31) / 32)), dim3(32 * kFinishGroups), 0, s, partial, nblocks,
-                       d, out);
+                       d, out, ldp > 0 ? ldp : d);
 }
 
 void launch_add_padded(float* out, const float* z, int64_t rows, int32_t d, int32_t ldz,
-                       const float* bias, int accumulate, int relu, hipStream_t s)
+                       const float* bias, int accumulate, int relu, hipStream_t s, int32_t ldo)
 {
     if (rows <= 0 || d <= 0) return;
     int64_t blocks = (rows * d + kBlock - 1) / kBlock;
     if (blocks > 65536) blocks = 65536;
     hipLaunchKernelGGL(k_add_padded, dim3((unsigned)blocks), dim3(kBlock), 0, s, out, z, rows, d, ldz, bias,
-                       accumulate, relu);
+                       accumulate, relu, ldo > 0 ? ldo : d);
 }
 
 void launch_bias_act_bf16(void* out, const float* z, int64_t rows, int32_t d, int32_t ldz, const float* bias,
@@ -738,12 +738,12 @@ void launch_bias_act_bf16(void* out, const float* z, int64_t rows, int32_t d, in
                        ldz, bias, relu);
 }
 
-void launch_pad_rows(float* dst, const float* src, int64_t rows, int32_t d, int32_t ld, hipStream_t s)
+void launch_pad_rows(float* dst, const float* src, int64_t rows, int32_t d, int32_t ld, hipStream_t s, int32_t lds)
 {
     if (rows <= 0 || ld <= 0) return;
     int64_t blocks = (rows * ld + kBlock - 1) / kBlock;
     if (blocks > 65536) blocks = 65536;
-    hipLaunchKernelGGL(k_pad_rows, dim3((unsigned)blocks), dim3(kBlock), 0, s, dst, src, rows, d, ld);
+    hipLaunchKernelGGL(k_pad_rows, dim3((unsigned)blocks), dim3(kBlock), 0, s, dst, src, rows, d, ld, lds > 0 ? lds : d);
 }
 
 void launch_adam(float* w, const float* g, float* m, float* v, int64_t n, float lr, float beta1,

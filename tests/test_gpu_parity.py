@@ -1253,6 +1253,58 @@ def test_graph_attention_epoch_matches_oracle(name, dims, k, mode):
             assert np.array_equal(a, b), key
 
 
+@pytest.mark.parametrize("name,dims,heads,k,mode", [
+    ("mini_sage", (24, 32, 16, 8), (4, 2, 1), 5, "lp"),                  # heads of 8 columns
+    ("mini_gcn_directed", (20, 15, 12, 6), (3, 4, 2), 7, "random"),      # 5- and 3-column heads: padded, unaligned slices of W
+    ("tiny", (64, 64, 16), (8, 2), 4, "switching"),                      # hub rows cut into segments, per head
+    ("mini_sage", (24, 256, 7), (4, 1), 1, "random"),                    # 64-column heads, k = 1
+])
+def test_multi_head_attention_epoch_matches_oracle(name, dims, heads, k, mode):
+    """Several attention heads per layer (gnn_set_gat_heads): every array of the epoch against the
+    oracle's multi-head layer, two epochs giving the same bits, and heads = 1 written out giving
+    the bits of the default."""
+    say("case multi-head attention %s %s heads=%s k=%d" % (name, dims, heads, k))
+    from oracle import gat as ogat
+    from paper_2605_11517_amd import Session
+    cfg, rowptr, colidx = make_config(name, dims=dims)
+    n = cfg["n"]
+    L = len(dims) - 1
+    X = features(n, dims[0], cfg["seed"])
+    y, m = labels_and_mask(n, dims[-1], cfg["train_frac"], cfg["seed"])
+    w = gat_weights(dims, cfg["seed"])
+    for wl, h in zip(w, heads):
+        wl["heads"] = h
+    ref = ogat.epoch(rowptr, colidx, dims, X, w, y, m)
+    s = Session("gat", dims, rowptr, colidx, k, mode, cfg["seed"], X, w, y, m)
+    loss = s.epoch()
+    assert abs(loss - ref["loss"]) <= TOL * abs(ref["loss"]), (loss, ref["loss"])
+    got = s.results()
+    worst = {}
+    for l in range(L):
+        worst["act[%d]" % l] = rel_err(got["act"][l], ref["act"][l])
+        worst["gact[%d]" % l] = rel_err(got["gact"][l], ref["gact"][l])
+        worst["gW[%d]" % l] = rel_err(got["gW"][l], ref["gW"][l])
+        ga_ref = np.stack([ref["ga_src"][l], ref["ga_dst"][l]])
+        worst["ga[%d]" % l] = rel_err(got["gWs"][l], ga_ref)
+        worst["gb[%d]" % l] = rel_err(got["gb"][l], ref["gb"][l])
+    say("  worst rel err %.3g" % max(worst.values()))
+    bad = {key: v for key, v in worst.items() if not (v <= TOL)}
+    assert not bad, bad
+    assert s.epoch() == loss
+    r2 = s.results()
+    for key in ("act", "gact", "gW", "gWs", "gb"):
+        for a, b in zip(got[key], r2[key]):
+            assert np.array_equal(a, b), key
+    # the heads matter: the one-head model of the same weights gives another loss
+    for wl in w:
+        wl["heads"] = 1
+    one = Session("gat", dims, rowptr, colidx, k, mode, cfg["seed"], X, w, y, m)
+    l1 = one.epoch()
+    assert abs(l1 - loss) > 1e-4 * abs(loss), (l1, loss)
+    ref1 = ogat.epoch(rowptr, colidx, dims, X, [{q: v for q, v in wl.items() if q != "heads"} for wl in w], y, m)
+    assert abs(l1 - ref1["loss"]) <= TOL * abs(ref1["loss"])
+
+
 # ----------------------------------------------------------------------------------------
 # measurement hooks
 # ----------------------------------------------------------------------------------------

@@ -243,3 +243,19 @@ def test_errors_of_the_training_order_and_attention_entry_points():
     for p in range(3):
         assert np.array_equal(gat.get_boundary(p), gcn.get_boundary(p))
     assert all(gat.layer_is_transform_first(l) for l in (1, 2))
+    # attention heads: for GNN_GAT only, a divisor of the layer's width, and they enlarge the workspace
+    with pytest.raises(GnnError) as e:
+        gcn.set_gat_heads(1, 2)
+    assert e.value.status == 1
+    for layer, heads in ((0, 1), (3, 1), (1, 3), (1, 0), (2, 8), (1, 128)):
+        with pytest.raises(GnnError) as e:
+            gat.set_gat_heads(layer, heads)
+        assert e.value.status == 1, (layer, heads)
+    before = gat.workspace_bytes()
+    gat.set_gat_heads(1, 4)
+    gat.set_gat_heads(2, 2)
+    after = gat.workspace_bytes()
+    assert after[0] >= before[0] and after[1] > before[1]
+    gat.set_gat_heads(1, 1)
+    gat.set_gat_heads(2, 1)
+    assert gat.workspace_bytes() == before
