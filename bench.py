@@ -134,6 +134,9 @@ def oracle_epoch_seconds(cfg, rowptr, colidx, X, w, y, m):
     return time.perf_counter() - t0
 
 
+GAT_HEADS = None     # --gat-heads: attention heads per layer of the graph-attention workloads
+
+
 def make_inputs(name, cfg_over):
     from synth import attention_vectors, features, glorot_weights, labels_and_mask, make_config
     cfg, rowptr, colidx = make_config(name, **cfg_over)
@@ -143,6 +146,11 @@ def make_inputs(name, cfg_over):
     w = glorot_weights(dims, cfg["seed"], sage=(model == "sage"))
     if model == "gat":
         attention_vectors(w, cfg["seed"])
+        if GAT_HEADS:
+            if len(GAT_HEADS) != len(w):
+                raise SystemExit("--gat-heads needs one head count per layer (%d)" % len(w))
+            for wl, h in zip(w, GAT_HEADS):
+                wl["heads"] = h
     return cfg, rowptr, colidx, X, y, m, w
 
 
@@ -354,6 +362,7 @@ def run_workload(name, args, steps, warmup, want_cpu):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg["dtype"], "data": "synthetic",
         "config": {"workload": name + ("" if args.graph_scale == 1.0 else " x%g" % args.graph_scale) +
+                               (" heads=%s" % args.gat_heads if args.gat_heads and model == "gat" else "") +
                    ("" if not budget else " (streaming, %.3g GiB block cache)" % (budget / 2 ** 30)),
                    "n": n, "operator_entries": nnz, "model": model,
                    "dims": list(dims), "k": stats["k"], "partitioner": cfg["part"],
@@ -498,6 +507,8 @@ def main():
     ap.add_argument("--graph-scale", type=float, default=1.0,
                     help="shrink the workload's graph (vertices and drawn edges) by this factor; "
                          "for runs that would not fit the host otherwise")
+    ap.add_argument("--gat-heads", default=None,
+                    help="graph-attention workloads: attention heads per layer, comma-separated (e.g. 8,8,1)")
     ap.add_argument("--train", action="store_true",
                     help="time training steps instead of bare epochs: epoch with dropout 0.5 after "
                          "the hidden layers, then one Adam step (lr 0.01), as in the paper's runs")
@@ -528,6 +539,9 @@ def main():
     ap.add_argument("--no-profile", action="store_true",
                     help="leave the per-kernel HIP events out of the timed region")
     args = ap.parse_args()
+    if args.gat_heads:
+        global GAT_HEADS
+        GAT_HEADS = [int(h) for h in args.gat_heads.split(",")]
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no sharding or collectives are "
                  "built); run with --gpus 1")

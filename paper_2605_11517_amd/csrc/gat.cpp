@@ -21,11 +21,14 @@ namespace {
 // One head of a layer on one partition.  With one head: f = d_l, fp = the padded row width, and
 // every offset below is zero.  With several, head j is a layer of its own on columns
 // [j f, (j + 1) f) of W, of the attention vectors, of the bias and of the output, with its own
-// arrays of H, grad H (fp floats per vertex) and scores (one float per vertex).
+// arrays of H and grad H (fp floats per vertex) and of attention weights and edge-wise products
+// (`hs` floats per head); the scores of a vertex lie side by side, nh floats per vertex, so that
+// the row-wise passes fetch a neighbour's scores once for all heads (they run all heads in one
+// launch; the pointers below then are head 0's).
 struct GatView {
-    int64_t r0, np, nb, e0, n;
+    int64_t r0, np, nb, e0, n, hs;
     int32_t din, dout, nh, f, fp;
-    float *H, *gH, *ssrc, *sdst, *gssrc, *gsdst, *bs, *att, *dal, *twatt, *stg;
+    float *H, *gH, *ssrc, *sdst, *gssrc, *gsdst, *bs, *att, *dal, *twatt, *pair, *stg;
     const float *W, *a_src, *a_dst;
 };
 
@@ -46,15 +49,18 @@ GatView view(gnn_ctx* c, int32_t layer, int32_t p, int32_t h)
     char* sc = c->scratch;
     v.H = (float*)c->hbuf + (int64_t)h * v.n * v.fp;
     v.gH = (float*)c->ghbuf + (int64_t)h * v.n * v.fp;
-    v.ssrc = (float*)(sc + c->ws.ssrc) + (int64_t)h * v.n;
-    v.sdst = (float*)(sc + c->ws.sdst) + (int64_t)h * v.n;
-    v.gssrc = (float*)(sc + c->ws.gssrc) + (int64_t)h * v.n;
-    v.gsdst = (float*)(sc + c->ws.gsdst) + (int64_t)h * v.n;
-    v.bs = (float*)(sc + c->ws.bs) + (int64_t)h * v.nb;
+    // scores: element (vertex r, head h) at [r nh + h]
+    v.ssrc = (float*)(sc + c->ws.ssrc) + h;
+    v.sdst = (float*)(sc + c->ws.sdst) + h;
+    v.gssrc = (float*)(sc + c->ws.gssrc) + h;
+    v.gsdst = (float*)(sc + c->ws.gsdst) + h;
+    v.bs = (float*)(sc + c->ws.bs) + h;
     v.stg = (float*)c->staging + (int64_t)h * v.nb * v.fp;
-    v.att = (float*)(sc + c->ws.att);
-    v.dal = (float*)(sc + c->ws.dal);
-    v.twatt = (float*)(sc + c->ws.twatt);
+    v.hs = M.stats.max_nnz;
+    v.att = (float*)(sc + c->ws.att) + (int64_t)h * v.hs;
+    v.dal = (float*)(sc + c->ws.dal) + (int64_t)h * v.hs;
+    v.twatt = (float*)(sc + c->ws.twatt) + (int64_t)h * v.hs;
+    v.pair = (float*)(sc + c->ws.pair);       // (att, dpre) of every entry and head, entry-major
     v.W = (const float*)c->w[(size_t)3 * (layer - 1)] + (int64_t)h * v.f;
     v.a_src = (const float*)c->w[(size_t)3 * (layer - 1) + 1] + (int64_t)h * v.f;
     v.a_dst = v.a_src + v.dout;
@@ -68,9 +74,11 @@ GatRowsHost rows_of(gnn_ctx* c, const GatView& v, int32_t p)
     h.col = c->D.lcol;
     h.e0 = v.e0;
     h.n_own = v.np;
-    h.ssrc_own = v.ssrc + v.r0;
+    h.ssrc_own = v.ssrc + v.r0 * v.nh;
     h.ssrc_bnd = v.bs;
-    h.sdst_own = v.sdst + v.r0;
+    h.sdst_own = v.sdst + v.r0 * v.nh;
+    h.nh = v.nh;
+    h.hs = v.hs;
     h.items = plan_items(c->M.plan_fwd, c->D.fwd, p);
     return h;
 }
@@ -95,7 +103,7 @@ void gat_transform_fwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
             launch_gemm_nn(&seg, 1, Hp, v.fp, v.np, v.f, GemmEpilogue{}, s);
         }
         Timed t(c, s, GNN_K_OTHER);
-        launch_gat_scores(Hp, v.fp, v.f, v.np, v.a_src, v.a_dst, v.ssrc + v.r0, v.sdst + v.r0, s);
+        launch_gat_scores(Hp, v.fp, v.f, v.np, v.a_src, v.a_dst, v.ssrc + v.r0 * v.nh, v.sdst + v.r0 * v.nh, v.nh, s);
     }
 }
 
@@ -108,7 +116,7 @@ void gat_gather(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
     for (int32_t h = 0; h < nh; ++h) {
         const GatView v = view(c, layer, p, h);
         launch_gather_rows(v.H, bnd, v.stg, v.nb, (int64_t)v.fp * 4, s);
-        launch_gather_rows(v.ssrc, bnd, v.bs, v.nb, 4, s);
+        if (h == 0) launch_gather_rows(v.ssrc, bnd, v.bs, v.nb, (int64_t)nh * 4, s);   // all heads' scores
     }
 }
 
@@ -117,13 +125,15 @@ void gat_layer_fwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
     const int32_t nh = c->nheads(layer);
     float* Z = (float*)(c->scratch + c->ws.z);
     float* segpart = (float*)(c->scratch + c->ws.segpart);
+    {
+        // attention weights of every head
+        const GatView v = view(c, layer, p, 0);
+        Timed t(c, s, GNN_K_OTHER);
+        launch_gat_attention(rows_of(c, v, p), v.att, segpart, s);
+    }
     for (int32_t h = 0; h < nh; ++h) {
         const GatView v = view(c, layer, p, h);
         const GatRowsHost rows = rows_of(c, v, p);
-        {
-            Timed t(c, s, GNN_K_OTHER);
-            launch_gat_attention(rows, v.att, segpart, s);
-        }
         {
             Timed t(c, s, GNN_K_SPMM);
             launch_spmm(rows.rp, rows.col, v.att - v.e0, nullptr, v.H + v.r0 * v.fp, v.np, v.stg, Z, v.np, v.fp,
@@ -177,32 +187,36 @@ void gat_layer_bwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
     const SpmmItems titems = plan_items(M.plan_bwd, c->D.bwd, p);
     const int32_t* bnd = c->D.bnd + M.boff[(size_t)p];
     float* segpart = (float*)(c->scratch + c->ws.segpart);
+    const GatRowsHost rows = rows_of(c, v0, p);
+    {
+        // recompute the attention weights of every head from the regathered scores
+        Timed t(c, s, GNN_K_OTHER);
+        launch_gat_attention(rows, v0.att, segpart, s);
+    }
+    // the head's columns of dY as rows of fp floats, head after head (np fp floats each)
+    float* pad = (float*)(c->scratch + c->ws.dz);
+    const bool padded = nh > 1 || v0.fp != v0.f;
     for (int32_t h = 0; h < nh; ++h) {
         const GatView v = view(c, layer, p, h);
-        const GatRowsHost rows = rows_of(c, v, p);
-        // the head's columns of dY as rows of fp floats
         const float* dYp = dY;
-        if (nh > 1 || v.fp != v.f) {
+        if (padded) {
             Timed t(c, s, GNN_K_OTHER);
-            float* pad = (float*)(c->scratch + c->ws.dz);
-            launch_pad_rows(pad, dY + (int64_t)h * v.f, v.np, v.f, v.fp, s, v.dout);
-            dYp = pad;
+            float* ph = pad + (int64_t)h * v.np * v.fp;
+            launch_pad_rows(ph, dY + (int64_t)h * v.f, v.np, v.f, v.fp, s, v.dout);
+            dYp = ph;
         }
-        {
-            // recompute the attention weights from the regathered scores
-            Timed t(c, s, GNN_K_OTHER);
-            launch_gat_attention(rows, v.att, segpart, s);
-        }
-        {
-            Timed t(c, s, GNN_K_SPMM);      // edge-wise products: one source row read per entry
-            launch_gat_dots(rows.rp, rows.col, v.e0, v.np, v.H + v.r0 * v.fp, v.stg, dYp, v.fp, v.dal, rows.items, s);
-        }
-        {
-            Timed t(c, s, GNN_K_OTHER);
-            launch_gat_bwd_scalars(rows, v.att, v.dal, v.gsdst + v.r0, segpart, s);
-            launch_gat_transposed(c->D.trp + t0, c->D.tperm, v.e0, v.np, v.r0, bnd, titems, v.att, v.dal, v.twatt,
-                                  v.gssrc, s);
-        }
+        Timed t(c, s, GNN_K_SPMM);      // edge-wise products: one source row read per entry
+        launch_gat_dots(rows.rp, rows.col, v.e0, v.np, v.H + v.r0 * v.fp, v.stg, dYp, v.fp, v.dal, rows.items, s);
+    }
+    {
+        Timed t(c, s, GNN_K_OTHER);     // every head
+        launch_gat_bwd_scalars(rows, v0.att, v0.dal, v0.pair, v0.gsdst + v0.r0 * nh, segpart, s);
+        launch_gat_transposed(c->D.trp + t0, c->D.tperm, v0.e0, v0.np, v0.r0, bnd, titems, v0.pair, v0.twatt,
+                              v0.gssrc, nh, v0.hs, s);
+    }
+    for (int32_t h = 0; h < nh; ++h) {
+        const GatView v = view(c, layer, p, h);
+        const float* dYp = padded ? pad + (int64_t)h * v.np * v.fp : dY;
         SpmmScatter sc;
         sc.n_own = v.np;
         sc.base_row = v.r0;
@@ -230,7 +244,8 @@ void gat_transform_bwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
         const float* Hp = v.H + v.r0 * v.fp;
         {
             Timed t(c, s, GNN_K_OTHER);
-            launch_gat_rank1(gHp, Hp, v.fp, v.f, v.np, v.gssrc + v.r0, v.gsdst + v.r0, v.a_src, v.a_dst, part, s);
+            launch_gat_rank1(gHp, Hp, v.fp, v.f, v.np, v.gssrc + v.r0 * nh, v.gsdst + v.r0 * nh, nh, v.a_src, v.a_dst,
+                             part, s);
             if (nh == 1) {
                 launch_colsum_finish(part, (v.np + 255) / 256, 2 * v.dout, ga, s);
             } else {

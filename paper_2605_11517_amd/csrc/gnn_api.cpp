@@ -329,15 +329,16 @@ void compute_workspace(gnn_ctx* c)
         }
     }
     if (c->model == GNN_GAT) {
-        const int64_t mh = c->max_heads();      // per-vertex scores: one array of n floats per head
+        const int64_t mh = c->max_heads();      // per-vertex scores: the heads' values side by side
         w.ssrc = take(M.n * mh);
         w.sdst = take(M.n * mh);
         w.gssrc = take(M.n * mh);
         w.gsdst = take(M.n * mh);
         w.bs = take(max_b * mh);
-        w.att = take(M.stats.max_nnz);
-        w.dal = take(M.stats.max_nnz);
-        w.twatt = take(M.stats.max_nnz);
+        w.att = take(M.stats.max_nnz * mh);     // per-entry arrays: one per head
+        w.dal = take(M.stats.max_nnz * mh);
+        w.twatt = take(M.stats.max_nnz * mh);
+        w.pair = take(M.stats.max_nnz * mh * 2);
     }
     w.scratch_bytes = o;
 }

@@ -66,8 +66,9 @@ struct Workspace {  // byte offsets into `scratch`
     // the previous partition still reads the other one on the side stream
     int64_t z2 = 0;
     // graph attention: per-vertex scores and their gradients, staged boundary scores, per-entry
-    // attention weights, edge-wise products, attention weights in transposed order
-    int64_t ssrc = 0, sdst = 0, gssrc = 0, gsdst = 0, bs = 0, att = 0, dal = 0, twatt = 0;
+    // attention weights, edge-wise products, attention weights in transposed order, and the
+    // (attention weight, score gradient) pairs of all heads per entry
+    int64_t ssrc = 0, sdst = 0, gssrc = 0, gsdst = 0, bs = 0, att = 0, dal = 0, twatt = 0, pair = 0;
     int64_t staging_bytes = 0, scratch_bytes = 0;
 };
 

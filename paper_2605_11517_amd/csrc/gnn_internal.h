@@ -273,7 +273,10 @@ void launch_global_columns(const int32_t* lcol, int32_t* gcol, int64_t count, in
 // ---- graph attention (kernels_gat.hip) ----------------------------------------------------
 // Rows of one partition for the row-wise attention passes: rp points at the partition's first
 // row pointer, col / att / dal are indexed with absolute positions (minus e0 for the
-// per-partition arrays), s_src of a local column c is ssrc_own[c] or ssrc_bnd[c - n_own].
+// per-partition arrays).  nh heads: the scores of a vertex are nh floats side by side (s_src of a
+// local column c and head h is ssrc_own[c nh + h] or ssrc_bnd[(c - n_own) nh + h]), the per-entry
+// arrays (att, dal, tw_att) are one array per head, hs floats apart; the passes below handle all
+// heads in one launch.
 struct GatRowsHost {
     const int64_t* rp = nullptr;
     const int32_t* col = nullptr;
@@ -281,30 +284,37 @@ struct GatRowsHost {
     const float* ssrc_own = nullptr;
     const float* ssrc_bnd = nullptr;
     const float* sdst_own = nullptr;
+    int32_t nh = 1;
+    int64_t hs = 0;
     SpmmItems items;
 };
+// one head: ssrc[r nh] = H[r, :f] . a_src, sdst[r nh] = H[r, :f] . a_dst for `rows` rows
 void launch_gat_scores(const float* H, int32_t ld, int32_t f, int64_t rows, const float* a_src,
-                       const float* a_dst, float* ssrc, float* sdst, hipStream_t s);
+                       const float* a_dst, float* ssrc, float* sdst, int32_t nh, hipStream_t s);
 // att[e - e0] = softmax over each row of LeakyReLU_0.2(s_src(col e) + s_dst(row))
-// segwork: 3 floats per segment of the partition's long rows (scratch of the segment-parallel passes)
+// segwork: 3 floats per head and segment of the partition's long rows (scratch of the segment-parallel passes)
 void launch_gat_attention(const GatRowsHost& h, float* att, float* segwork, hipStream_t s);
 // dal[e - e0] = dy[row,:] . src(col e)[:]  (rows of width ld, a multiple of 4)
 void launch_gat_dots(const int64_t* rp, const int32_t* col, int64_t e0, int64_t n_own, const float* a_rows,
                      const float* b_rows, const float* dy, int32_t ld, float* dal, const SpmmItems& items,
                      hipStream_t s);
-// dal <- gradient of the pre-activation scores (through softmax and LeakyReLU); gs_dst_own[row] = row sum
-void launch_gat_bwd_scalars(const GatRowsHost& h, const float* att, float* dal, float* gs_dst_own,
-                            float* segwork, hipStream_t s);
-// transposed rows: tw_att[pos - e0] = att[tperm[pos]]; with dpre != null also
-// gs_src[owner row of transposed row i] += sum over the row of dpre[tperm[pos]]
+// gradient of the pre-activation scores (through softmax and LeakyReLU) from att and dal, every
+// head: pair[((e - e0) nh + h) 2 + {0, 1}] = att, dpre (an entry's values of all heads side by
+// side, for the transposed pass); gs_dst_own[row nh + h] = row sum of dpre
+void launch_gat_bwd_scalars(const GatRowsHost& h, const float* att, const float* dal, float* pair,
+                            float* gs_dst_own, float* segwork, hipStream_t s);
+// transposed rows, every head: tw_att[h hs + pos - e0] = att of entry tperm[pos];
+// gs_src[(owner row of transposed row i) nh + h] += sum over the row of dpre of entry tperm[pos]
 void launch_gat_transposed(const int64_t* trp, const int32_t* tperm, int64_t e0, int64_t n_own,
-                           int64_t base_row, const int32_t* bnd, const SpmmItems& items, const float* att,
-                           const float* dpre, float* tw_att, float* gs_src, hipStream_t s);
-// gH += gs_src a_src^T + gs_dst a_dst^T over `rows` rows; partial column sums of gs_src H and
-// gs_dst H (2 f floats per block of 256 rows) for the gradients of the attention vectors
+                           int64_t base_row, const int32_t* bnd, const SpmmItems& items, const float* pair,
+                           float* tw_att, float* gs_src, int32_t nh, int64_t hs, hipStream_t s);
+// one head: gH += gs_src a_src^T + gs_dst a_dst^T over `rows` rows (the head's scores nh floats
+// apart); partial column sums of gs_src H and gs_dst H (2 f floats per block of 256 rows) for
+// the gradients of the attention vectors
 int64_t gat_rank1_partial_floats(int64_t rows, int32_t f);
 void launch_gat_rank1(float* gH, const float* H, int32_t ld, int32_t f, int64_t rows, const float* gs_src,
-                      const float* gs_dst, const float* a_src, const float* a_dst, float* partial, hipStream_t s);
+                      const float* gs_dst, int32_t nh, const float* a_src, const float* a_dst, float* partial,
+                      hipStream_t s);
 // out[c] += sum over b < nblocks of partial[b * ldp + c] for c < d (ldp = 0: rows of d floats)
 void launch_colsum_finish(const float* partial, int64_t nblocks, int32_t d, float* out, hipStream_t s,
                           int32_t ldp = 0);

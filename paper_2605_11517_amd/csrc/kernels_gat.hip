@@ -1,10 +1,15 @@
-// Kernels of the graph-attention layers (one head, LeakyReLU slope 0.2; Velickovic et al.,
+// Kernels of the graph-attention layers (LeakyReLU slope 0.2; Velickovic et al.,
 // the model family the paper evaluates next to GCN and GraphSAGE).  A layer transforms first:
 // H = A^{l-1} W, s_src = H a_src, s_dst = H a_dst per vertex; a partition then gathers the rows
 // of H and the scores s_src of its boundary vertices, computes the attention weight of every
 // entry of T_p and aggregates with them (the aggregation kernel of the other models, with the
 // attention weights as entry weights).  The backward pass regathers, recomputes the attention
 // weights and needs one more edge-wise kernel: the dot product dY[v] . H[u] per entry.
+//
+// Several heads: the per-vertex scores of all heads of a vertex lie side by side (nh floats per
+// vertex, so one fetch of a neighbour's scores serves every head), the per-entry arrays (attention
+// weights, edge-wise products) are kept head after head, `hs` floats apart, and the row-wise
+// passes walk the heads of a row one after the other.
 //
 // Row-wise scalar passes: a wavefront walks the short rows of a range item one after the other;
 // long rows are cut into the aggregation kernel's segments, one wavefront per segment, and
@@ -46,24 +51,30 @@ struct GatRows {
     const int32_t* col;         // local columns (absolute positions)
     int64_t e0;                 // first absolute position of the partition
     int64_t n_own;
-    const float* ssrc_own;      // s_src of the partition's own rows
-    const float* ssrc_bnd;      // s_src of its boundary rows (staged)
-    const float* sdst_own;
+    const float* ssrc_own;      // s_src of the partition's own rows, nh floats per row
+    const float* ssrc_bnd;      // s_src of its boundary rows (staged), nh floats per row
+    const float* sdst_own;      // nh floats per row
+    int32_t nh;                 // heads
+    int64_t hs;                 // floats between two heads' per-entry arrays
     // work decomposition
     const int32_t* range_rows;
     int64_t nranges;
     const int32_t* long_row;
     int64_t nlong;
-    __device__ float ssrc(int32_t c) const { return c < n_own ? ssrc_own[c] : ssrc_bnd[c - n_own]; }
+    __device__ float ssrc(int32_t c, int32_t h) const
+    {
+        return c < n_own ? ssrc_own[(int64_t)c * nh + h] : ssrc_bnd[(int64_t)(c - n_own) * nh + h];
+    }
 };
 
 __device__ inline float lrelu(float x) { return x > 0.f ? x : kSlope * x; }
 
-// s_src[r] = H[r,:] . a_src, s_dst[r] = H[r,:] . a_dst; one wavefront per row
+// s_src[r nh] = H[r,:] . a_src, s_dst[r nh] = H[r,:] . a_dst; one wavefront per row
 __global__ __launch_bounds__(kBlock) void k_gat_scores(const float* __restrict__ H, int32_t ld, int32_t f,
                                                        int64_t rows, const float* __restrict__ a_src,
                                                        const float* __restrict__ a_dst,
-                                                       float* __restrict__ ssrc, float* __restrict__ sdst)
+                                                       float* __restrict__ ssrc, float* __restrict__ sdst,
+                                                       int32_t nh)
 {
     const int lane = threadIdx.x % kWave;
     const int64_t r = (int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;
@@ -77,8 +88,8 @@ __global__ __launch_bounds__(kBlock) void k_gat_scores(const float* __restrict__
     s1 = wave_sum(s1);
     s2 = wave_sum(s2);
     if (lane == 0) {
-        ssrc[r] = s1;
-        sdst[r] = s2;
+        ssrc[r * nh] = s1;
+        sdst[r * nh] = s2;
     }
 }
 
@@ -87,93 +98,177 @@ __global__ __launch_bounds__(kBlock) void k_gat_scores(const float* __restrict__
 // lane keeps its up to eight scores in registers, so the scores are gathered once.
 constexpr int kPerLane = kSpmmSegment / kWave;
 
-__device__ inline void att_row_wave(const GatRows& g, int32_t row, float* __restrict__ att)
+// The row-wise passes take HB heads of a row at a time (h0 .. h0 + HB - 1, those below nh):
+// the scores of the HB heads of a neighbour lie side by side and are fetched together (VEC: as
+// one 16-byte vector; needs HB = 4 and nh a multiple of 4), and the HB reductions run beside
+// each other instead of one after the other.
+template <int HB, bool VEC>
+__device__ inline void load_scores(const GatRows& g, int32_t c, int32_t h0, int nhb, float (&out)[HB])
+{
+    const float* p = c < g.n_own ? g.ssrc_own + (int64_t)c * g.nh + h0
+                                 : g.ssrc_bnd + (int64_t)(c - g.n_own) * g.nh + h0;
+    if (VEC) {
+        static_assert(!VEC || HB == 4, "vector loads take four heads");
+        const float4 v = *reinterpret_cast<const float4*>(p);
+        out[0] = v.x; out[1 % HB] = v.y; out[2 % HB] = v.z; out[3 % HB] = v.w;
+    } else {
+#pragma unroll
+        for (int b = 0; b < HB; ++b) out[b] = b < nhb ? p[b] : 0.f;
+    }
+}
+
+template <int HB, bool VEC>
+__device__ inline void att_row_wave(const GatRows& g, int32_t row, int32_t h0, float* __restrict__ att_all)
 {
     const int t = threadIdx.x % kWave;
+    const int nhb = g.nh - h0 < HB ? g.nh - h0 : HB;
     const int64_t eb = g.rp[row], ee = g.rp[row + 1];
     const int niter = (int)((ee - eb + kWave - 1) / kWave);
-    const float sd = g.sdst_own[row];
-    float x[kPerLane];
-    float m = -INFINITY;
+    float sd[HB], m[HB];
+#pragma unroll
+    for (int b = 0; b < HB; ++b) {
+        sd[b] = b < nhb ? g.sdst_own[(int64_t)row * g.nh + h0 + b] : 0.f;
+        m[b] = -INFINITY;
+    }
+    float x[HB][kPerLane];
 #pragma unroll
     for (int i = 0; i < kPerLane; ++i) {
-        x[i] = -INFINITY;
+#pragma unroll
+        for (int b = 0; b < HB; ++b) x[b][i] = -INFINITY;
         if (i < niter) {
             const int64_t e = eb + t + (int64_t)i * kWave;
-            if (e < ee) x[i] = lrelu(g.ssrc(g.col[e]) + sd);
-            m = fmaxf(m, x[i]);
+            if (e < ee) {
+                float sc[HB];
+                load_scores<HB, VEC>(g, g.col[e], h0, nhb, sc);
+#pragma unroll
+                for (int b = 0; b < HB; ++b) x[b][i] = lrelu(sc[b] + sd[b]);
+            }
+#pragma unroll
+            for (int b = 0; b < HB; ++b) m[b] = fmaxf(m[b], x[b][i]);
         }
     }
-    m = wave_max(m);
-    float s = 0.f;
+    float s[HB];
+#pragma unroll
+    for (int b = 0; b < HB; ++b) {
+        m[b] = wave_max(m[b]);
+        s[b] = 0.f;
+    }
 #pragma unroll
     for (int i = 0; i < kPerLane; ++i)
         if (i < niter) {
-            x[i] = expf(x[i] - m);          // exp(-inf) = 0 for the lanes past the row end
-            s += x[i];
+#pragma unroll
+            for (int b = 0; b < HB; ++b) {
+                x[b][i] = expf(x[b][i] - m[b]);          // exp(-inf) = 0 for the lanes past the row end
+                s[b] += x[b][i];
+            }
         }
-    s = wave_sum(s);
-    const float inv = 1.f / s;
+#pragma unroll
+    for (int b = 0; b < HB; ++b) s[b] = 1.f / wave_sum(s[b]);
 #pragma unroll
     for (int i = 0; i < kPerLane; ++i)
         if (i < niter) {
             const int64_t e = eb + t + (int64_t)i * kWave;
-            if (e < ee) att[e - g.e0] = x[i] * inv;
+            if (e < ee) {
+#pragma unroll
+                for (int b = 0; b < HB; ++b)
+                    if (b < nhb) att_all[(h0 + b) * g.hs + (e - g.e0)] = x[b][i] * s[b];
+            }
         }
 }
 
 // after the edge-wise dot products dal[e] = dY[row] . H[col]: t = sum att dal;
-// dal[e] <- att (dal - t) LeakyReLU'(x)  (gradient of the pre-activation score);
-// gs_dst[row] = sum of those
-__device__ inline void bwd_row_wave(const GatRows& g, int32_t row, const float* __restrict__ att,
-                                    float* __restrict__ dal, float* __restrict__ gs_dst_own)
+// dpre[e] = att (dal - t) LeakyReLU'(x)  (gradient of the pre-activation score);
+// gs_dst[row] = sum of those.  The pairs (att, dpre) of an entry are written side by side for
+// all heads, pair[((e - e0) nh + h) 2 + {0, 1}]: the transposed pass fetches an entry's values by
+// position, and finds those of every head in one place.
+template <int HB, bool VEC>
+__device__ inline void bwd_row_wave(const GatRows& g, int32_t row, int32_t h0, const float* __restrict__ att_all,
+                                    const float* __restrict__ dal_all, float* __restrict__ pair,
+                                    float* __restrict__ gs_dst_own)
 {
+    static_assert(HB == 1 || HB == 2, "pairs of one or two heads");
     const int t = threadIdx.x % kWave;
+    const int nhb = g.nh - h0 < HB ? g.nh - h0 : HB;
     const int64_t eb = g.rp[row], ee = g.rp[row + 1];
     const int niter = (int)((ee - eb + kWave - 1) / kWave);
-    const float sd = g.sdst_own[row];
-    float a[kPerLane], d[kPerLane], sl[kPerLane];
-    float tv = 0.f;
+    float sd[HB], tv[HB];
+#pragma unroll
+    for (int b = 0; b < HB; ++b) {
+        sd[b] = b < nhb ? g.sdst_own[(int64_t)row * g.nh + h0 + b] : 0.f;
+        tv[b] = 0.f;
+    }
+    float a[HB][kPerLane], d[HB][kPerLane], sl[HB][kPerLane];
 #pragma unroll
     for (int i = 0; i < kPerLane; ++i) {
-        a[i] = 0.f; d[i] = 0.f; sl[i] = 0.f;
+#pragma unroll
+        for (int b = 0; b < HB; ++b) { a[b][i] = 0.f; d[b][i] = 0.f; sl[b][i] = 0.f; }
         if (i < niter) {
             const int64_t e = eb + t + (int64_t)i * kWave;
             if (e < ee) {
-                a[i] = att[e - g.e0];
-                d[i] = dal[e - g.e0];
-                sl[i] = (g.ssrc(g.col[e]) + sd) > 0.f ? 1.f : kSlope;
+                float sc[HB];
+                load_scores<HB, false>(g, g.col[e], h0, nhb, sc);
+#pragma unroll
+                for (int b = 0; b < HB; ++b)
+                    if (b < nhb) {
+                        a[b][i] = att_all[(h0 + b) * g.hs + (e - g.e0)];
+                        d[b][i] = dal_all[(h0 + b) * g.hs + (e - g.e0)];
+                        sl[b][i] = (sc[b] + sd[b]) > 0.f ? 1.f : kSlope;
+                    }
             }
-            tv += a[i] * d[i];
+#pragma unroll
+            for (int b = 0; b < HB; ++b) tv[b] += a[b][i] * d[b][i];
         }
     }
-    tv = wave_sum(tv);
-    float ds = 0.f;
+    float ds[HB];
+#pragma unroll
+    for (int b = 0; b < HB; ++b) {
+        tv[b] = wave_sum(tv[b]);
+        ds[b] = 0.f;
+    }
 #pragma unroll
     for (int i = 0; i < kPerLane; ++i)
         if (i < niter) {
             const int64_t e = eb + t + (int64_t)i * kWave;
-            const float dp = a[i] * (d[i] - tv) * sl[i];
-            if (e < ee) dal[e - g.e0] = dp;
-            ds += dp;
+            float dp[HB];
+#pragma unroll
+            for (int b = 0; b < HB; ++b) {
+                dp[b] = a[b][i] * (d[b][i] - tv[b]) * sl[b][i];
+                ds[b] += dp[b];
+            }
+            if (e < ee) {
+                float* q = pair + ((e - g.e0) * g.nh + h0) * 2;
+                if (HB == 2 && VEC) {
+                    *reinterpret_cast<float4*>(q) = make_float4(a[0][i], dp[0], a[HB - 1][i], dp[HB - 1]);
+                } else {
+#pragma unroll
+                    for (int b = 0; b < HB; ++b)
+                        if (b < nhb) *reinterpret_cast<float2*>(q + 2 * b) = make_float2(a[b][i], dp[b]);
+                }
+            }
         }
-    ds = wave_sum(ds);
-    if (t == 0) gs_dst_own[row] = ds;
+#pragma unroll
+    for (int b = 0; b < HB; ++b) {
+        ds[b] = wave_sum(ds[b]);
+        if (t == 0 && b < nhb) gs_dst_own[(int64_t)row * g.nh + h0 + b] = ds[b];
+    }
 }
 
 // MODE 0: attention weights; MODE 1: backward scalars.  One range item of short rows per
 // wavefront; long rows are skipped here and handled segment by segment below.
-template <int MODE>
+template <int MODE, int HB, bool VEC>
 __global__ __launch_bounds__(kBlock) void k_gat_rows(const GatRows g, float* __restrict__ att,
-                                                     float* __restrict__ dal, float* __restrict__ gs_dst_own)
+                                                     float* __restrict__ dal, float* __restrict__ pair,
+                                                     float* __restrict__ gs_dst_own)
 {
     const int64_t item = (int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;
     if (item >= g.nranges) return;
     const int32_t r1 = g.range_rows[item + 1];
     for (int32_t row = g.range_rows[item]; row < r1; ++row) {
         if (g.rp[row + 1] - g.rp[row] > kSpmmSegment) continue;
-        if (MODE == 0) att_row_wave(g, row, att);
-        else bwd_row_wave(g, row, att, dal, gs_dst_own);
+        for (int32_t h0 = 0; h0 < g.nh; h0 += HB) {
+            if constexpr (MODE == 0) att_row_wave<HB, VEC>(g, row, h0, att);
+            else bwd_row_wave<HB, VEC>(g, row, h0, att, dal, pair, gs_dst_own);
+        }
     }
 }
 
@@ -195,187 +290,235 @@ struct GatSegs {
 // STEP 0: per segment local max m and sum of exp(x - m); att <- exp(x - m)
 // STEP 1: att *= factor[segment]
 // STEP 2: per segment sum of att * dal
-// STEP 3: dal <- att (dal - t[segment]) LeakyReLU'(x); per segment sum of those
+// STEP 3: dpre = att (dal - t[segment]) LeakyReLU'(x) written beside att into `pair` (see
+//         bwd_row_wave); per segment sum of those
 template <int STEP>
 __global__ __launch_bounds__(kBlock) void k_gat_segments(const GatRows g, const GatSegs q,
-                                                         float* __restrict__ att, float* __restrict__ dal,
-                                                         float* __restrict__ stat, const float* __restrict__ factor)
+                                                         float* __restrict__ att_all, float* __restrict__ dal_all,
+                                                         float* __restrict__ stat_all,
+                                                         const float* __restrict__ factor_all,
+                                                         float* __restrict__ pair)
 {
     const int t = threadIdx.x % kWave;
     const int64_t sgi = (int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;
     if (sgi >= q.nsegs) return;
     const int32_t row = q.seg_row[sgi];
     const int64_t eb = q.seg_begin[sgi], ee = eb + q.seg_len[sgi];
-    const float sd = g.sdst_own[row];
-    if (STEP == 0) {
-        float x[kPerLane];
-        float m = -INFINITY;
+    for (int32_t h = 0; h < g.nh; ++h) {
+        // head h: per-entry arrays hs floats on, per-segment arrays 2 nsegs (stat) / nsegs (factor) on
+        float* __restrict__ att = att_all + h * g.hs;
+        float* __restrict__ dal = dal_all ? dal_all + h * g.hs : nullptr;
+        float* __restrict__ stat = stat_all ? stat_all + (int64_t)h * 2 * q.nsegs : nullptr;
+        const float* __restrict__ factor = factor_all ? factor_all + (int64_t)h * q.nsegs : nullptr;
+        const float sd = g.sdst_own[(int64_t)row * g.nh + h];
+        if (STEP == 0) {
+            float x[kPerLane];
+            float m = -INFINITY;
 #pragma unroll
-        for (int i = 0; i < kPerLane; ++i) {
-            const int64_t e = eb + t + (int64_t)i * kWave;
-            x[i] = e < ee ? lrelu(g.ssrc(g.col[e]) + sd) : -INFINITY;
-            m = fmaxf(m, x[i]);
-        }
-        m = wave_max(m);
-        float sum = 0.f;
-#pragma unroll
-        for (int i = 0; i < kPerLane; ++i) {
-            const int64_t e = eb + t + (int64_t)i * kWave;
-            const float ex = expf(x[i] - m);
-            if (e < ee) att[e - g.e0] = ex;
-            sum += ex;
-        }
-        sum = wave_sum(sum);
-        if (t == 0) {
-            stat[2 * sgi] = m;
-            stat[2 * sgi + 1] = sum;
-        }
-    } else if (STEP == 1) {
-        const float f = factor[sgi];
-        for (int64_t e = eb + t; e < ee; e += kWave) att[e - g.e0] *= f;
-    } else if (STEP == 2) {
-        float tv = 0.f;
-        for (int64_t e = eb + t; e < ee; e += kWave) tv += att[e - g.e0] * dal[e - g.e0];
-        tv = wave_sum(tv);
-        if (t == 0) stat[sgi] = tv;
-    } else {
-        const float tv = factor[sgi];
-        float ds = 0.f;
-#pragma unroll
-        for (int i = 0; i < kPerLane; ++i) {
-            const int64_t e = eb + t + (int64_t)i * kWave;
-            if (e < ee) {
-                const float x = g.ssrc(g.col[e]) + sd;
-                const float dp = att[e - g.e0] * (dal[e - g.e0] - tv) * (x > 0.f ? 1.f : kSlope);
-                dal[e - g.e0] = dp;
-                ds += dp;
+            for (int i = 0; i < kPerLane; ++i) {
+                const int64_t e = eb + t + (int64_t)i * kWave;
+                x[i] = e < ee ? lrelu(g.ssrc(g.col[e], h) + sd) : -INFINITY;
+                m = fmaxf(m, x[i]);
             }
+            m = wave_max(m);
+            float sum = 0.f;
+#pragma unroll
+            for (int i = 0; i < kPerLane; ++i) {
+                const int64_t e = eb + t + (int64_t)i * kWave;
+                const float ex = expf(x[i] - m);
+                if (e < ee) att[e - g.e0] = ex;
+                sum += ex;
+            }
+            sum = wave_sum(sum);
+            if (t == 0) {
+                stat[2 * sgi] = m;
+                stat[2 * sgi + 1] = sum;
+            }
+        } else if (STEP == 1) {
+            const float f = factor[sgi];
+            for (int64_t e = eb + t; e < ee; e += kWave) att[e - g.e0] *= f;
+        } else if (STEP == 2) {
+            float tv = 0.f;
+            for (int64_t e = eb + t; e < ee; e += kWave) tv += att[e - g.e0] * dal[e - g.e0];
+            tv = wave_sum(tv);
+            if (t == 0) stat[sgi] = tv;
+        } else {
+            const float tv = factor[sgi];
+            float ds = 0.f;
+#pragma unroll
+            for (int i = 0; i < kPerLane; ++i) {
+                const int64_t e = eb + t + (int64_t)i * kWave;
+                if (e < ee) {
+                    const float x = g.ssrc(g.col[e], h) + sd;
+                    const float av = att[e - g.e0];
+                    const float dp = av * (dal[e - g.e0] - tv) * (x > 0.f ? 1.f : kSlope);
+                    *reinterpret_cast<float2*>(pair + ((e - g.e0) * g.nh + h) * 2) = make_float2(av, dp);
+                    ds += dp;
+                }
+            }
+            ds = wave_sum(ds);
+            if (t == 0) stat[sgi] = ds;
         }
-        ds = wave_sum(ds);
-        if (t == 0) stat[sgi] = ds;
     }
 }
 
-// One wavefront per long row, its segments in ascending order.
+// One wavefront per long row, its segments in ascending order, head after head.
 // STEP 0: from (m, sum) per segment: factor[segment] = exp(m_seg - M) / S
 // STEP 2: factor[segment] = sum of the row's stat (the row's t)
 // STEP 3: gs_dst_own[row] = sum of the row's stat
 template <int STEP>
-__global__ __launch_bounds__(kBlock) void k_gat_combine(const GatSegs q, const float* __restrict__ stat,
-                                                        float* __restrict__ factor, float* __restrict__ gs_dst_own)
+__global__ __launch_bounds__(kBlock) void k_gat_combine(const GatSegs q, int32_t nh,
+                                                        const float* __restrict__ stat_all,
+                                                        float* __restrict__ factor_all,
+                                                        float* __restrict__ gs_dst_own)
 {
     const int t = threadIdx.x % kWave;
     const int64_t i = (int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;
     if (i >= q.nlong) return;
     const int32_t first = q.long_first[i], ns = q.long_nseg[i];
-    if (STEP == 0) {
-        float M = -INFINITY;
-        for (int32_t j = t; j < ns; j += kWave) M = fmaxf(M, stat[2 * (int64_t)(first + j)]);
-        M = wave_max(M);
-        float S = 0.f;
-        for (int32_t j = t; j < ns; j += kWave)
-            S += stat[2 * (int64_t)(first + j) + 1] * expf(stat[2 * (int64_t)(first + j)] - M);
-        S = wave_sum(S);
-        const float inv = 1.f / S;
-        for (int32_t j = t; j < ns; j += kWave) factor[first + j] = expf(stat[2 * (int64_t)(first + j)] - M) * inv;
-    } else {
-        float v = 0.f;
-        for (int32_t j = t; j < ns; j += kWave) v += stat[first + j];
-        v = wave_sum(v);
-        if (STEP == 2) {
-            for (int32_t j = t; j < ns; j += kWave) factor[first + j] = v;
-        } else if (t == 0) {
-            gs_dst_own[q.long_row[i]] = v;
+    for (int32_t h = 0; h < nh; ++h) {
+        const float* __restrict__ stat = stat_all + (int64_t)h * 2 * q.nsegs;
+        float* __restrict__ factor = factor_all ? factor_all + (int64_t)h * q.nsegs : nullptr;
+        if (STEP == 0) {
+            float M = -INFINITY;
+            for (int32_t j = t; j < ns; j += kWave) M = fmaxf(M, stat[2 * (int64_t)(first + j)]);
+            M = wave_max(M);
+            float S = 0.f;
+            for (int32_t j = t; j < ns; j += kWave)
+                S += stat[2 * (int64_t)(first + j) + 1] * expf(stat[2 * (int64_t)(first + j)] - M);
+            S = wave_sum(S);
+            const float inv = 1.f / S;
+            for (int32_t j = t; j < ns; j += kWave) factor[first + j] = expf(stat[2 * (int64_t)(first + j)] - M) * inv;
+        } else {
+            float v = 0.f;
+            for (int32_t j = t; j < ns; j += kWave) v += stat[first + j];
+            v = wave_sum(v);
+            if (STEP == 2) {
+                for (int32_t j = t; j < ns; j += kWave) factor[first + j] = v;
+            } else if (t == 0) {
+                gs_dst_own[(int64_t)q.long_row[i] * nh + h] = v;
+            }
         }
     }
 }
 
-// Rows of the transposed operator (the entries of R_p = [own ; boundary] as sources):
-// tw_att[pos - e0] = att[tperm[pos]] (entry weights of the transposed aggregation) and
-// gs_src[owner row of i] += sum over the row of dpre[tperm[pos]].
+// Rows of the transposed operator (the entries of R_p = [own ; boundary] as sources), every head:
+// tw_att[h hs + pos - e0] = att of entry tperm[pos] (entry weights of the transposed aggregation)
+// and gs_src[(owner row of i) nh + h] += sum over the row of dpre of entry tperm[pos], both read
+// from the pairs the backward scalar pass wrote (pair[(entry nh + h) 2 + {0, 1}] = att, dpre: the
+// values of all heads of an entry lie in one place, a fetch by position finds them together).
 struct GatTRows {
     const int64_t* trp;
     const int32_t* tperm;
     int64_t e0;
     int64_t n_own, base_row;
     const int32_t* bnd;         // library rows of the boundary vertices
+    int32_t nh;                 // heads: gs_src holds nh floats per vertex,
+    int64_t hs;                 // tw_att one array per head, hs floats apart
     const int32_t* range_rows;
     int64_t nranges;
     const int32_t* long_row;
     int64_t nlong;
 };
-template <bool BLOCK>
-__device__ inline void trow(const GatTRows& g, int32_t i, const float* __restrict__ att,
-                            const float* __restrict__ dpre, float* __restrict__ tw_att,
-                            float* __restrict__ gs_src, float* sm)
+// one head of one long transposed row, a workgroup per row
+__device__ inline void trow_block(const GatTRows& g, int32_t i, int32_t h, const float* __restrict__ pair,
+                                  float* __restrict__ tw_att, float* __restrict__ gs_src, float* sm)
 {
-    constexpr int T = BLOCK ? kBlock : kWave;
-    const int t = BLOCK ? threadIdx.x : threadIdx.x % kWave;
+    constexpr int T = kBlock;
+    const int t = threadIdx.x;
     const int64_t eb = g.trp[i], ee = g.trp[i + 1];
     float s = 0.f;
     constexpr int U = 4;
     for (int64_t e = eb + t; e < ee; e += (int64_t)T * U) {
         int32_t fe[U];
-        float av[U], dv[U];
+        float2 v[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int64_t eu = e + (int64_t)u * T;
             fe[u] = g.tperm[eu < ee ? eu : ee - 1];
         }
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            av[u] = att[fe[u]];
-            dv[u] = dpre ? dpre[fe[u]] : 0.f;
-        }
+        for (int u = 0; u < U; ++u)
+            v[u] = *reinterpret_cast<const float2*>(pair + ((int64_t)fe[u] * g.nh + h) * 2);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int64_t eu = e + (int64_t)u * T;
             if (eu < ee) {
-                tw_att[eu - g.e0] = av[u];
-                s += dv[u];
+                tw_att[h * g.hs + eu - g.e0] = v[u].x;
+                s += v[u].y;
             }
         }
     }
-    if (!dpre) return;
-    s = red_sum<BLOCK>(s, sm);
+    s = red_sum<true>(s, sm);
     if (t == 0) {
         const int64_t r = i < g.n_own ? g.base_row + i : (int64_t)g.bnd[i - g.n_own];
-        gs_src[r] += s;
+        gs_src[r * g.nh + h] += s;
     }
 }
-template <bool BLOCK>
-__global__ __launch_bounds__(kBlock) void k_gat_trows(const GatTRows g, const float* __restrict__ att,
-                                                      const float* __restrict__ dpre,
+// EVEN: nh is even, two heads' pairs are read as one 16-byte vector
+template <bool BLOCK, bool EVEN>
+__global__ __launch_bounds__(kBlock) void k_gat_trows(const GatTRows g, const float* __restrict__ pair,
                                                       float* __restrict__ tw_att, float* __restrict__ gs_src)
 {
     __shared__ float sm[kBlock / kWave];
     if (BLOCK) {
         const int64_t i = blockIdx.x;
         if (i >= g.nlong) return;
-        trow<true>(g, g.long_row[i], att, dpre, tw_att, gs_src, sm);
+        for (int32_t h = 0; h < g.nh; ++h) trow_block(g, g.long_row[i], h, pair, tw_att, gs_src, sm);
     } else {
         // transposed rows are short (a source feeds about ten destinations of a partition): a
-        // group of 16 lanes takes a row, four rows of the item at a time
-        constexpr int GW = 16;
+        // group of 16 lanes takes a row, four rows of the item at a time, four heads at a time
+        constexpr int GW = 16, HB = 4;
         const int lane = threadIdx.x % kWave, gl = lane % GW, grp = lane / GW;
         const int64_t item = (int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;
         if (item >= g.nranges) return;
         const int32_t r1 = g.range_rows[item + 1];
-        for (int32_t i = g.range_rows[item] + grp; i < r1; i += kWave / GW) {
-            const int64_t eb = g.trp[i], ee = g.trp[i + 1];
-            if (ee - eb > kSpmmSegment) continue;
-            float sum = 0.f;
-            for (int64_t e = eb + gl; e < ee; e += GW) {
-                const int32_t fe = g.tperm[e];
-                tw_att[e - g.e0] = att[fe];
-                if (dpre) sum += dpre[fe];
+        // (every lane of the wavefront runs the same number of row steps: the shuffles below
+        // need all 64 lanes; lanes without a row take an empty one)
+        for (int32_t i0 = g.range_rows[item]; i0 < r1; i0 += kWave / GW) {
+            const int32_t i = i0 + grp;
+            int64_t eb = 0, ee = 0;
+            if (i < r1) {
+                eb = g.trp[i];
+                ee = g.trp[i + 1];
+                if (ee - eb > kSpmmSegment) ee = eb;      // long rows: the other kernel
             }
-            if (dpre) {
+            for (int32_t h0 = 0; h0 < g.nh; h0 += HB) {
+                const int nhb = g.nh - h0 < HB ? g.nh - h0 : HB;
+                float sum[HB] = {0.f, 0.f, 0.f, 0.f};
+                for (int64_t e = eb + gl; e < ee; e += GW) {
+                    const float* q = pair + ((int64_t)g.tperm[e] * g.nh + h0) * 2;
+                    float av[HB], dv[HB];
+                    if (EVEN) {
 #pragma unroll
-                for (int m = 1; m < GW; m <<= 1) sum += __shfl_xor(sum, m, kWave);
-                if (gl == 0) {
-                    const int64_t r = i < g.n_own ? g.base_row + i : (int64_t)g.bnd[i - g.n_own];
-                    gs_src[r] += sum;
+                        for (int b = 0; b < HB; b += 2) {
+                            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                            if (b < nhb) v = *reinterpret_cast<const float4*>(q + 2 * b);
+                            av[b] = v.x; dv[b] = v.y; av[b + 1] = v.z; dv[b + 1] = v.w;
+                        }
+                    } else {
+#pragma unroll
+                        for (int b = 0; b < HB; ++b) {
+                            float2 v = make_float2(0.f, 0.f);
+                            if (b < nhb) v = *reinterpret_cast<const float2*>(q + 2 * b);
+                            av[b] = v.x; dv[b] = v.y;
+                        }
+                    }
+#pragma unroll
+                    for (int b = 0; b < HB; ++b)
+                        if (b < nhb) {
+                            tw_att[(h0 + b) * g.hs + e - g.e0] = av[b];
+                            sum[b] += dv[b];
+                        }
+                }
+#pragma unroll
+                for (int b = 0; b < HB; ++b) {
+#pragma unroll
+                    for (int m = 1; m < GW; m <<= 1) sum[b] += __shfl_xor(sum[b], m, kWave);
+                    if (gl == 0 && b < nhb && ee > eb) {
+                        const int64_t r = i < g.n_own ? g.base_row + i : (int64_t)g.bnd[i - g.n_own];
+                        gs_src[r * g.nh + h0 + b] += sum[b];
+                    }
                 }
             }
         }
@@ -474,7 +617,8 @@ __global__ __launch_bounds__(kBlock) void k_gat_dots(const GatDotArgs g)
     }
 }
 
-// gH[r, j] += gs_src[r] a_src[j] + gs_dst[r] a_dst[j] for the rows of one partition, and the
+// gH[r, j] += gs_src[r nh] a_src[j] + gs_dst[r nh] a_dst[j] for the rows of one partition (one
+// head: its scores are nh floats apart), and the
 // per-block partial column sums  sum_r gs_src[r] H[r, j]  (first f columns of `partial` rows) and
 // sum_r gs_dst[r] H[r, j]  (next f columns), 256 rows per block.
 __global__ __launch_bounds__(kBlock) void k_gat_rank1(float* __restrict__ gH, const float* __restrict__ H,
@@ -483,7 +627,7 @@ __global__ __launch_bounds__(kBlock) void k_gat_rank1(float* __restrict__ gH, co
                                                       const float* __restrict__ gs_dst,
                                                       const float* __restrict__ a_src,
                                                       const float* __restrict__ a_dst,
-                                                      float* __restrict__ partial)
+                                                      float* __restrict__ partial, int32_t nh)
 {
     const int64_t r0 = (int64_t)blockIdx.x * 256;
     const int64_t r1 = r0 + 256 < rows ? r0 + 256 : rows;
@@ -491,7 +635,7 @@ __global__ __launch_bounds__(kBlock) void k_gat_rank1(float* __restrict__ gH, co
         const float as = a_src[j], ad = a_dst[j];
         float p1 = 0.f, p2 = 0.f;
         for (int64_t r = r0; r < r1; ++r) {
-            const float gs = gs_src[r], gd = gs_dst[r];
+            const float gs = gs_src[r * nh], gd = gs_dst[r * nh];
             const float h = H[r * ld + j];
             gH[r * ld + j] += gs * as + gd * ad;
             p1 += gs * h;
@@ -502,15 +646,56 @@ __global__ __launch_bounds__(kBlock) void k_gat_rank1(float* __restrict__ gH, co
     }
 }
 
+// The same for rows of at most CW <= 128 columns: the 256 threads form kBlock / CW row groups of
+// CW columns, each group takes every (kBlock / CW)-th row of the block's 256, and the groups'
+// partial column sums are combined in group order.
+template <int CW>
+__global__ __launch_bounds__(kBlock) void k_gat_rank1_narrow(float* __restrict__ gH, const float* __restrict__ H,
+                                                             int32_t ld, int32_t f, int64_t rows,
+                                                             const float* __restrict__ gs_src,
+                                                             const float* __restrict__ gs_dst,
+                                                             const float* __restrict__ a_src,
+                                                             const float* __restrict__ a_dst,
+                                                             float* __restrict__ partial, int32_t nh)
+{
+    constexpr int RG = kBlock / CW;
+    __shared__ float sm[RG][CW][2];
+    const int j = threadIdx.x % CW, rgp = threadIdx.x / CW;
+    const int64_t r0 = (int64_t)blockIdx.x * 256;
+    const int64_t r1 = r0 + 256 < rows ? r0 + 256 : rows;
+    float p1 = 0.f, p2 = 0.f;
+    if (j < f) {
+        const float as = a_src[j], ad = a_dst[j];
+        for (int64_t r = r0 + rgp; r < r1; r += RG) {
+            const float gs = gs_src[r * nh], gd = gs_dst[r * nh];
+            const float h = H[r * ld + j];
+            gH[r * ld + j] += gs * as + gd * ad;
+            p1 += gs * h;
+            p2 += gd * h;
+        }
+    }
+    sm[rgp][j][0] = p1;
+    sm[rgp][j][1] = p2;
+    __syncthreads();
+    if (rgp == 0 && j < f) {
+        for (int q = 1; q < RG; ++q) {
+            p1 += sm[q][j][0];
+            p2 += sm[q][j][1];
+        }
+        partial[(int64_t)blockIdx.x * 2 * f + j] = p1;
+        partial[(int64_t)blockIdx.x * 2 * f + f + j] = p2;
+    }
+}
+
 }  // namespace
 
 void launch_gat_scores(const float* H, int32_t ld, int32_t f, int64_t rows, const float* a_src,
-                       const float* a_dst, float* ssrc, float* sdst, hipStream_t s)
+                       const float* a_dst, float* ssrc, float* sdst, int32_t nh, hipStream_t s)
 {
     if (rows <= 0) return;
     const int64_t blocks = (rows + kBlock / kWave - 1) / (kBlock / kWave);
     hipLaunchKernelGGL(k_gat_scores, dim3((unsigned)blocks), dim3(kBlock), 0, s, H, ld, f, rows, a_src, a_dst,
-                       ssrc, sdst);
+                       ssrc, sdst, nh);
 }
 
 static GatRows make_rows(const GatRowsHost& h)
@@ -518,6 +703,7 @@ static GatRows make_rows(const GatRowsHost& h)
     GatRows g;
     g.rp = h.rp; g.col = h.col; g.e0 = h.e0; g.n_own = h.n_own;
     g.ssrc_own = h.ssrc_own; g.ssrc_bnd = h.ssrc_bnd; g.sdst_own = h.sdst_own;
+    g.nh = h.nh; g.hs = h.hs;
     g.range_rows = h.items.range_rows; g.nranges = h.items.nranges;
     g.long_row = h.items.long_row; g.nlong = h.items.nlong;
     return g;
@@ -533,58 +719,70 @@ static GatSegs make_segs(const GatRowsHost& h)
     return q;
 }
 
-// `segwork`: 3 floats per segment of the partition's long rows
+// `segwork`: 3 floats per head and segment of the partition's long rows
 void launch_gat_attention(const GatRowsHost& h, float* att, float* segwork, hipStream_t s)
 {
     const GatRows g = make_rows(h);
-    if (g.nranges > 0)
-        hipLaunchKernelGGL((k_gat_rows<0>), dim3((unsigned)((g.nranges + 3) / 4)), dim3(kBlock), 0, s, g,
-                           att, (float*)nullptr, (float*)nullptr);
+    if (g.nranges > 0) {
+        const dim3 grid((unsigned)((g.nranges + 3) / 4)), b(kBlock);
+        float* none = nullptr;
+        if (g.nh == 1) hipLaunchKernelGGL((k_gat_rows<0, 1, false>), grid, b, 0, s, g, att, none, none, none);
+        else if (g.nh % 4 == 0) hipLaunchKernelGGL((k_gat_rows<0, 4, true>), grid, b, 0, s, g, att, none, none, none);
+        else hipLaunchKernelGGL((k_gat_rows<0, 4, false>), grid, b, 0, s, g, att, none, none, none);
+    }
     const GatSegs q = make_segs(h);
     if (q.nsegs > 0 && q.nlong > 0) {
         float* stat = segwork;
-        float* factor = segwork + 2 * q.nsegs;
+        float* factor = segwork + 2 * q.nsegs * g.nh;
+        float* none = nullptr;
         const dim3 gs((unsigned)((q.nsegs + 3) / 4)), gl((unsigned)((q.nlong + 3) / 4)), b(kBlock);
-        hipLaunchKernelGGL((k_gat_segments<0>), gs, b, 0, s, g, q, att, (float*)nullptr, stat, (const float*)nullptr);
-        hipLaunchKernelGGL((k_gat_combine<0>), gl, b, 0, s, q, (const float*)stat, factor, (float*)nullptr);
-        hipLaunchKernelGGL((k_gat_segments<1>), gs, b, 0, s, g, q, att, (float*)nullptr, (float*)nullptr,
-                           (const float*)factor);
+        hipLaunchKernelGGL((k_gat_segments<0>), gs, b, 0, s, g, q, att, none, stat, (const float*)nullptr, none);
+        hipLaunchKernelGGL((k_gat_combine<0>), gl, b, 0, s, q, g.nh, (const float*)stat, factor, none);
+        hipLaunchKernelGGL((k_gat_segments<1>), gs, b, 0, s, g, q, att, none, none, (const float*)factor, none);
     }
 }
 
-void launch_gat_bwd_scalars(const GatRowsHost& h, const float* att, float* dal, float* gs_dst_own,
-                            float* segwork, hipStream_t s)
+void launch_gat_bwd_scalars(const GatRowsHost& h, const float* att, const float* dal, float* pair,
+                            float* gs_dst_own, float* segwork, hipStream_t s)
 {
     const GatRows g = make_rows(h);
-    if (g.nranges > 0)
-        hipLaunchKernelGGL((k_gat_rows<1>), dim3((unsigned)((g.nranges + 3) / 4)), dim3(kBlock), 0, s, g,
-                           const_cast<float*>(att), dal, gs_dst_own);
+    float* a = const_cast<float*>(att);
+    float* d = const_cast<float*>(dal);
+    if (g.nranges > 0) {
+        const dim3 grid((unsigned)((g.nranges + 3) / 4)), b(kBlock);
+        if (g.nh == 1) hipLaunchKernelGGL((k_gat_rows<1, 1, false>), grid, b, 0, s, g, a, d, pair, gs_dst_own);
+        else if (g.nh % 2 == 0) hipLaunchKernelGGL((k_gat_rows<1, 2, true>), grid, b, 0, s, g, a, d, pair, gs_dst_own);
+        else hipLaunchKernelGGL((k_gat_rows<1, 2, false>), grid, b, 0, s, g, a, d, pair, gs_dst_own);
+    }
     const GatSegs q = make_segs(h);
     if (q.nsegs > 0 && q.nlong > 0) {
         float* stat = segwork;
-        float* factor = segwork + 2 * q.nsegs;
-        float* a = const_cast<float*>(att);
+        float* factor = segwork + 2 * q.nsegs * g.nh;
+        float* none = nullptr;
         const dim3 gs((unsigned)((q.nsegs + 3) / 4)), gl((unsigned)((q.nlong + 3) / 4)), b(kBlock);
-        hipLaunchKernelGGL((k_gat_segments<2>), gs, b, 0, s, g, q, a, dal, stat, (const float*)nullptr);
-        hipLaunchKernelGGL((k_gat_combine<2>), gl, b, 0, s, q, (const float*)stat, factor, (float*)nullptr);
-        hipLaunchKernelGGL((k_gat_segments<3>), gs, b, 0, s, g, q, a, dal, stat, (const float*)factor);
-        hipLaunchKernelGGL((k_gat_combine<3>), gl, b, 0, s, q, (const float*)stat, (float*)nullptr, gs_dst_own);
+        hipLaunchKernelGGL((k_gat_segments<2>), gs, b, 0, s, g, q, a, d, stat, (const float*)nullptr, none);
+        hipLaunchKernelGGL((k_gat_combine<2>), gl, b, 0, s, q, g.nh, (const float*)stat, factor, none);
+        hipLaunchKernelGGL((k_gat_segments<3>), gs, b, 0, s, g, q, a, d, stat, (const float*)factor, pair);
+        hipLaunchKernelGGL((k_gat_combine<3>), gl, b, 0, s, q, g.nh, (const float*)stat, none, gs_dst_own);
     }
 }
 
 void launch_gat_transposed(const int64_t* trp, const int32_t* tperm, int64_t e0, int64_t n_own,
-                           int64_t base_row, const int32_t* bnd, const SpmmItems& items, const float* att,
-                           const float* dpre, float* tw_att, float* gs_src, hipStream_t s)
+                           int64_t base_row, const int32_t* bnd, const SpmmItems& items, const float* pair,
+                           float* tw_att, float* gs_src, int32_t nh, int64_t hs, hipStream_t s)
 {
     GatTRows g;
     g.trp = trp; g.tperm = tperm; g.e0 = e0; g.n_own = n_own; g.base_row = base_row; g.bnd = bnd;
+    g.nh = nh; g.hs = hs;
     g.range_rows = items.range_rows; g.nranges = items.nranges;
     g.long_row = items.long_row; g.nlong = items.nlong;
-    if (g.nranges > 0)
-        hipLaunchKernelGGL((k_gat_trows<false>), dim3((unsigned)((g.nranges + 3) / 4)), dim3(kBlock), 0, s, g, att,
-                           dpre, tw_att, gs_src);
+    if (g.nranges > 0) {
+        const dim3 grid((unsigned)((g.nranges + 3) / 4)), b(kBlock);
+        if (nh % 2 == 0) hipLaunchKernelGGL((k_gat_trows<false, true>), grid, b, 0, s, g, pair, tw_att, gs_src);
+        else hipLaunchKernelGGL((k_gat_trows<false, false>), grid, b, 0, s, g, pair, tw_att, gs_src);
+    }
     if (g.nlong > 0)
-        hipLaunchKernelGGL((k_gat_trows<true>), dim3((unsigned)g.nlong), dim3(kBlock), 0, s, g, att, dpre, tw_att,
+        hipLaunchKernelGGL((k_gat_trows<true, false>), dim3((unsigned)g.nlong), dim3(kBlock), 0, s, g, pair, tw_att,
                            gs_src);
 }
 
@@ -613,11 +811,22 @@ void launch_gat_dots(const int64_t* rp, const int32_t* col, int64_t e0, int64_t 
 int64_t gat_rank1_partial_floats(int64_t rows, int32_t f) { return ((rows + 255) / 256) * 2 * (int64_t)f; }
 
 void launch_gat_rank1(float* gH, const float* H, int32_t ld, int32_t f, int64_t rows, const float* gs_src,
-                      const float* gs_dst, const float* a_src, const float* a_dst, float* partial, hipStream_t s)
+                      const float* gs_dst, int32_t nh, const float* a_src, const float* a_dst, float* partial,
+                      hipStream_t s)
 {
     if (rows <= 0) return;
-    hipLaunchKernelGGL(k_gat_rank1, dim3((unsigned)((rows + 255) / 256)), dim3(kBlock), 0, s, gH, H, ld, f, rows,
-                       gs_src, gs_dst, a_src, a_dst, partial);
+    const dim3 grid((unsigned)((rows + 255) / 256)), b(kBlock);
+    if (f <= 32)
+        hipLaunchKernelGGL((k_gat_rank1_narrow<32>), grid, b, 0, s, gH, H, ld, f, rows, gs_src, gs_dst, a_src, a_dst,
+                           partial, nh);
+    else if (f <= 64)
+        hipLaunchKernelGGL((k_gat_rank1_narrow<64>), grid, b, 0, s, gH, H, ld, f, rows, gs_src, gs_dst, a_src, a_dst,
+                           partial, nh);
+    else if (f <= 128)
+        hipLaunchKernelGGL((k_gat_rank1_narrow<128>), grid, b, 0, s, gH, H, ld, f, rows, gs_src, gs_dst, a_src, a_dst,
+                           partial, nh);
+    else
+        hipLaunchKernelGGL(k_gat_rank1, grid, b, 0, s, gH, H, ld, f, rows, gs_src, gs_dst, a_src, a_dst, partial, nh);
 }
 
 }  // namespace gnnmi

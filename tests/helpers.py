@@ -212,7 +212,8 @@ def gat_sampled_errors(rowptr, colidx, dims, weights, X, act, gact, gb, V, say=N
     """Graph-attention layers checked on the sampled vertices ``V`` of a symmetric graph whose
     CSR holds no self-loops: rows ``V`` of every layer's output, every bias gradient, and rows
     ``V`` of every hidden input gradient, each recomputed in fp64 from the layer's definition
-    (one head, LeakyReLU slope 0.2, one self-loop per vertex) and from the given tensors of the
+    (``weights[l]["heads"]`` heads side by side, default one; LeakyReLU slope 0.2, one self-loop
+    per vertex) and from the given tensors of the
     step before (``act``: A^1..A^L, ``gact``: dLoss/dA^1..dLoss/dA^L).  Returns the relative
     errors by name.
 
@@ -240,48 +241,64 @@ def gat_sampled_errors(rowptr, colidx, dims, weights, X, act, gact, gb, V, say=N
         a_s = np.asarray(weights[l - 1]["a_src"], dtype=np.float64)
         a_d = np.asarray(weights[l - 1]["a_dst"], dtype=np.float64)
         b = np.asarray(weights[l - 1]["b"], dtype=np.float64)
+        # heads: head j is a one-head layer on columns cols[j] of H, a_src, a_dst and of the output
+        nh = int(weights[l - 1].get("heads", 1))
+        f = dims[l] // nh
+        cols = [slice(j * f, (j + 1) * f) for j in range(nh)]
         H = np.empty((n, dims[l]))
         for r0 in range(0, n, 1 << 18):
             H[r0:r0 + (1 << 18)] = np.asarray(A[l - 1][r0:r0 + (1 << 18)], dtype=np.float64) @ W
-        s_src, s_dst = H @ a_s, H @ a_d
+        s_src = np.stack([H[:, cj] @ a_s[cj] for cj in cols], axis=1)          # [n, heads]
+        s_dst = np.stack([H[:, cj] @ a_d[cj] for cj in cols], axis=1)
 
         # forward rows by the definition
         ref = []
         for v in V:
             u = around(v)
-            e = leaky(s_src[u] + s_dst[v])
-            ex = np.exp(e - e.max())
-            z = (ex / ex.sum()) @ H[u] + b
+            z = np.empty(dims[l])
+            for j, cj in enumerate(cols):
+                e = leaky(s_src[u, j] + s_dst[v, j])
+                ex = np.exp(e - e.max())
+                z[cj] = (ex / ex.sum()) @ H[u][:, cj]
+            z = z + b
             ref.append(np.maximum(z, 0.0) if l < L else z)
         worst["act[%d] rows" % (l - 1)] = rel_err(np.asarray(A[l])[V], np.array(ref))
 
         # per-vertex softmax statistics over all edges, then the input gradient of sampled rows
-        e = leaky(s_src[src] + s_dst[dst])
-        mx = np.full(n, -np.inf)
-        np.maximum.at(mx, dst, e)
-        den = np.zeros(n)
-        np.add.at(den, dst, np.exp(e - mx[dst]))
-        del e
+        mx = np.full((n, nh), -np.inf)
+        den = np.zeros((n, nh))
+        for j in range(nh):
+            e = leaky(s_src[src, j] + s_dst[dst, j])
+            m1 = np.full(n, -np.inf)
+            np.maximum.at(m1, dst, e)
+            d1 = np.zeros(n)
+            np.add.at(d1, dst, np.exp(e - m1[dst]))
+            mx[:, j], den[:, j] = m1, d1
+            del e
         dY = np.asarray(gact[l - 1], dtype=np.float64)
         if l < L:
             dY = np.where(np.asarray(A[l]) > 0, dY, 0.0)
-        c = np.einsum("ij,ij->i", dY, np.asarray(A[l], dtype=np.float64) - b)
+        Zb = np.asarray(A[l], dtype=np.float64) - b
+        c = np.stack([np.einsum("ij,ij->i", dY[:, cj], Zb[:, cj]) for cj in cols], axis=1)
+        del Zb
         worst["gb[%d]" % (l - 1)] = rel_err(gb[l - 1], dY.sum(axis=0))
         if l == 1:
             break                                   # the gradient of the input features is not kept
         ref = []
         for u in V:
             t = around(u)
-            # edges u -> t
-            x = s_src[u] + s_dst[t]
-            alpha = np.exp(leaky(x) - mx[t]) / den[t]
-            dx = alpha * (dY[t] @ H[u] - c[t]) * np.where(x > 0, 1.0, 0.2)
-            dH = alpha @ dY[t] + dx.sum() * a_s
-            # edges t -> u
-            x = s_src[t] + s_dst[u]
-            alpha = np.exp(leaky(x) - mx[u]) / den[u]
-            dx = alpha * (H[t] @ dY[u] - c[u]) * np.where(x > 0, 1.0, 0.2)
-            dH = dH + dx.sum() * a_d
+            dH = np.empty(dims[l])
+            for j, cj in enumerate(cols):
+                # edges u -> t
+                x = s_src[u, j] + s_dst[t, j]
+                alpha = np.exp(leaky(x) - mx[t, j]) / den[t, j]
+                dx = alpha * (dY[t][:, cj] @ H[u, cj] - c[t, j]) * np.where(x > 0, 1.0, 0.2)
+                dHj = alpha @ dY[t][:, cj] + dx.sum() * a_s[cj]
+                # edges t -> u
+                x = s_src[t, j] + s_dst[u, j]
+                alpha = np.exp(leaky(x) - mx[u, j]) / den[u, j]
+                dx = alpha * (H[t][:, cj] @ dY[u, cj] - c[u, j]) * np.where(x > 0, 1.0, 0.2)
+                dH[cj] = dHj + dx.sum() * a_d[cj]
             ref.append(dH @ W.T)
         worst["gact[%d] rows" % (l - 2)] = rel_err(np.asarray(gact[l - 2])[V], np.array(ref))
         if say:

@@ -379,8 +379,10 @@ def test_beyond_recipe_streams_below_its_working_set(capsys):
     assert not bad, bad
 
 
-def test_mid_gat_workload_sampled(capsys):
-    """Graph attention at the bench's `mid_gat` size.  A whole oracle epoch would need the
+@pytest.mark.parametrize("heads", [None, (8, 8, 1)], ids=["one_head", "eight_heads"])
+def test_mid_gat_workload_sampled(capsys, heads):
+    """Graph attention at the bench's `mid_gat` size, with one head per layer and with eight
+    32-column heads in the hidden layers.  A whole oracle epoch would need the
     edge-by-feature products of 134 M edges in memory; instead every layer's outputs and input
     gradients are recomputed for sampled vertices (eight hubs among them) from the layer's
     definition, one vertex at a time, from the path's own inputs to that step.  The softmax
@@ -405,7 +407,9 @@ def test_mid_gat_workload_sampled(capsys):
     X = features(n, dims[0], cfg["seed"])
     y, m = labels_and_mask(n, dims[-1], cfg["train_frac"], cfg["seed"])
     w = attention_vectors(glorot_weights(dims, cfg["seed"], sage=False, bias_scale=0.05), cfg["seed"])
-    say("inputs ready: n=%d entries=%d" % (n, rowptr[-1]))
+    for wl, h in zip(w, heads or ()):
+        wl["heads"] = h
+    say("inputs ready: n=%d entries=%d heads=%s" % (n, rowptr[-1], heads))
     s = Session("gat", dims, rowptr, colidx, cfg["k"], cfg["part"], cfg["seed"], X, w, y, m)
     loss = s.epoch()
     got = s.results()

@@ -141,13 +141,16 @@ def test_attention_is_invariant_to_a_shift_of_the_destination_score_sign_region(
     assert np.abs(cache3["alpha"][:6, 0] - want3).max() < 1e-14
 
 
-def test_sampled_row_check_agrees_with_the_whole_graph_epoch():
+@pytest.mark.parametrize("heads", [None, (3, 2, 1), (4, 5, 5)])
+def test_sampled_row_check_agrees_with_the_whole_graph_epoch(heads):
     """The per-vertex recomputation that the full-size GPU test uses (helpers.gat_sampled_errors)
     reproduces the oracle's whole-graph epoch on every vertex, and reports a planted mistake in
     an input gradient or an output row."""
     from helpers import gat_sampled_errors
     dims = (9, 12, 10, 5)
     rowptr, colidx, X, y, m, w = make(70, dims, seed=8)
+    for wl, h in zip(w, heads or ()):
+        wl["heads"] = h
     ref = gat.epoch(rowptr, colidx, dims, X, w, y, m)
     V = np.arange(70)
     errs = gat_sampled_errors(rowptr, colidx, dims, w, X, ref["act"], ref["gact"], ref["gb"], V)
