@@ -186,33 +186,35 @@ __device__ inline void bwd_row_wave(const GatRows& g, int32_t row, int32_t h0, c
                                     const float* __restrict__ dal_all, float* __restrict__ pair,
                                     float* __restrict__ gs_dst_own)
 {
-    static_assert(HB == 1 || HB == 2, "pairs of one or two heads");
+    static_assert(HB == 1 || HB == 2 || HB == 4, "blocks of one, two or four heads");
     const int t = threadIdx.x % kWave;
     const int nhb = g.nh - h0 < HB ? g.nh - h0 : HB;
     const int64_t eb = g.rp[row], ee = g.rp[row + 1];
     const int niter = (int)((ee - eb + kWave - 1) / kWave);
     float sd[HB], tv[HB];
+    unsigned pos[HB];           // bit i: the score of the lane's i-th entry is positive
 #pragma unroll
     for (int b = 0; b < HB; ++b) {
         sd[b] = b < nhb ? g.sdst_own[(int64_t)row * g.nh + h0 + b] : 0.f;
         tv[b] = 0.f;
+        pos[b] = 0u;
     }
-    float a[HB][kPerLane], d[HB][kPerLane], sl[HB][kPerLane];
+    float a[HB][kPerLane], d[HB][kPerLane];
 #pragma unroll
     for (int i = 0; i < kPerLane; ++i) {
 #pragma unroll
-        for (int b = 0; b < HB; ++b) { a[b][i] = 0.f; d[b][i] = 0.f; sl[b][i] = 0.f; }
+        for (int b = 0; b < HB; ++b) { a[b][i] = 0.f; d[b][i] = 0.f; }
         if (i < niter) {
             const int64_t e = eb + t + (int64_t)i * kWave;
             if (e < ee) {
                 float sc[HB];
-                load_scores<HB, false>(g, g.col[e], h0, nhb, sc);
+                load_scores<HB, VEC && HB == 4>(g, g.col[e], h0, nhb, sc);
 #pragma unroll
                 for (int b = 0; b < HB; ++b)
                     if (b < nhb) {
                         a[b][i] = att_all[(h0 + b) * g.hs + (e - g.e0)];
                         d[b][i] = dal_all[(h0 + b) * g.hs + (e - g.e0)];
-                        sl[b][i] = (sc[b] + sd[b]) > 0.f ? 1.f : kSlope;
+                        if (sc[b] + sd[b] > 0.f) pos[b] |= 1u << i;
                     }
             }
 #pragma unroll
@@ -232,13 +234,15 @@ __device__ inline void bwd_row_wave(const GatRows& g, int32_t row, int32_t h0, c
             float dp[HB];
 #pragma unroll
             for (int b = 0; b < HB; ++b) {
-                dp[b] = a[b][i] * (d[b][i] - tv[b]) * sl[b][i];
+                dp[b] = a[b][i] * (d[b][i] - tv[b]) * ((pos[b] >> i) & 1u ? 1.f : kSlope);
                 ds[b] += dp[b];
             }
             if (e < ee) {
                 float* q = pair + ((e - g.e0) * g.nh + h0) * 2;
-                if (HB == 2 && VEC) {
-                    *reinterpret_cast<float4*>(q) = make_float4(a[0][i], dp[0], a[HB - 1][i], dp[HB - 1]);
+                if (VEC) {          // whole blocks of an even number of heads: 16-byte stores
+#pragma unroll
+                    for (int b = 0; b + 1 < HB; b += 2)
+                        *reinterpret_cast<float4*>(q + 2 * b) = make_float4(a[b][i], dp[b], a[b + 1][i], dp[b + 1]);
                 } else {
 #pragma unroll
                     for (int b = 0; b < HB; ++b)
@@ -292,7 +296,9 @@ struct GatSegs {
 // STEP 2: per segment sum of att * dal
 // STEP 3: dpre = att (dal - t[segment]) LeakyReLU'(x) written beside att into `pair` (see
 //         bwd_row_wave); per segment sum of those
-template <int STEP>
+// Per-entry arrays of head h lie hs floats on, per-segment arrays 2 nsegs (stat) / nsegs (factor)
+// floats on.  Steps 0 and 3 take the heads in blocks of HB as the row-wise passes do.
+template <int STEP, int HB, bool VEC>
 __global__ __launch_bounds__(kBlock) void k_gat_segments(const GatRows g, const GatSegs q,
                                                          float* __restrict__ att_all, float* __restrict__ dal_all,
                                                          float* __restrict__ stat_all,
@@ -304,60 +310,109 @@ __global__ __launch_bounds__(kBlock) void k_gat_segments(const GatRows g, const 
     if (sgi >= q.nsegs) return;
     const int32_t row = q.seg_row[sgi];
     const int64_t eb = q.seg_begin[sgi], ee = eb + q.seg_len[sgi];
-    for (int32_t h = 0; h < g.nh; ++h) {
-        // head h: per-entry arrays hs floats on, per-segment arrays 2 nsegs (stat) / nsegs (factor) on
-        float* __restrict__ att = att_all + h * g.hs;
-        float* __restrict__ dal = dal_all ? dal_all + h * g.hs : nullptr;
-        float* __restrict__ stat = stat_all ? stat_all + (int64_t)h * 2 * q.nsegs : nullptr;
-        const float* __restrict__ factor = factor_all ? factor_all + (int64_t)h * q.nsegs : nullptr;
-        const float sd = g.sdst_own[(int64_t)row * g.nh + h];
-        if (STEP == 0) {
-            float x[kPerLane];
-            float m = -INFINITY;
+    if constexpr (STEP == 0) {
+        for (int32_t h0 = 0; h0 < g.nh; h0 += HB) {
+            const int nhb = g.nh - h0 < HB ? g.nh - h0 : HB;
+            float sd[HB], m[HB], sum[HB];
+#pragma unroll
+            for (int b = 0; b < HB; ++b) {
+                sd[b] = b < nhb ? g.sdst_own[(int64_t)row * g.nh + h0 + b] : 0.f;
+                m[b] = -INFINITY;
+                sum[b] = 0.f;
+            }
+            float x[HB][kPerLane];
 #pragma unroll
             for (int i = 0; i < kPerLane; ++i) {
                 const int64_t e = eb + t + (int64_t)i * kWave;
-                x[i] = e < ee ? lrelu(g.ssrc(g.col[e], h) + sd) : -INFINITY;
-                m = fmaxf(m, x[i]);
+#pragma unroll
+                for (int b = 0; b < HB; ++b) x[b][i] = -INFINITY;
+                if (e < ee) {
+                    float sc[HB];
+                    load_scores<HB, VEC>(g, g.col[e], h0, nhb, sc);
+#pragma unroll
+                    for (int b = 0; b < HB; ++b) x[b][i] = lrelu(sc[b] + sd[b]);
+                }
+#pragma unroll
+                for (int b = 0; b < HB; ++b) m[b] = fmaxf(m[b], x[b][i]);
             }
-            m = wave_max(m);
-            float sum = 0.f;
+#pragma unroll
+            for (int b = 0; b < HB; ++b) m[b] = wave_max(m[b]);
 #pragma unroll
             for (int i = 0; i < kPerLane; ++i) {
                 const int64_t e = eb + t + (int64_t)i * kWave;
-                const float ex = expf(x[i] - m);
-                if (e < ee) att[e - g.e0] = ex;
-                sum += ex;
+#pragma unroll
+                for (int b = 0; b < HB; ++b) {
+                    const float ex = expf(x[b][i] - m[b]);
+                    if (e < ee && b < nhb) att_all[(h0 + b) * g.hs + (e - g.e0)] = ex;
+                    sum[b] += ex;
+                }
             }
-            sum = wave_sum(sum);
-            if (t == 0) {
-                stat[2 * sgi] = m;
-                stat[2 * sgi + 1] = sum;
+#pragma unroll
+            for (int b = 0; b < HB; ++b) {
+                sum[b] = wave_sum(sum[b]);
+                if (t == 0 && b < nhb) {
+                    float* stat = stat_all + (int64_t)(h0 + b) * 2 * q.nsegs;
+                    stat[2 * sgi] = m[b];
+                    stat[2 * sgi + 1] = sum[b];
+                }
             }
-        } else if (STEP == 1) {
-            const float f = factor[sgi];
-            for (int64_t e = eb + t; e < ee; e += kWave) att[e - g.e0] *= f;
-        } else if (STEP == 2) {
-            float tv = 0.f;
-            for (int64_t e = eb + t; e < ee; e += kWave) tv += att[e - g.e0] * dal[e - g.e0];
-            tv = wave_sum(tv);
-            if (t == 0) stat[sgi] = tv;
-        } else {
-            const float tv = factor[sgi];
-            float ds = 0.f;
+        }
+    } else if constexpr (STEP == 3) {
+        static_assert(STEP != 3 || HB <= 2, "pairs of one or two heads");
+        for (int32_t h0 = 0; h0 < g.nh; h0 += HB) {
+            const int nhb = g.nh - h0 < HB ? g.nh - h0 : HB;
+            float sd[HB], tv[HB], ds[HB];
+#pragma unroll
+            for (int b = 0; b < HB; ++b) {
+                sd[b] = b < nhb ? g.sdst_own[(int64_t)row * g.nh + h0 + b] : 0.f;
+                tv[b] = b < nhb ? factor_all[(int64_t)(h0 + b) * q.nsegs + sgi] : 0.f;
+                ds[b] = 0.f;
+            }
 #pragma unroll
             for (int i = 0; i < kPerLane; ++i) {
                 const int64_t e = eb + t + (int64_t)i * kWave;
                 if (e < ee) {
-                    const float x = g.ssrc(g.col[e], h) + sd;
-                    const float av = att[e - g.e0];
-                    const float dp = av * (dal[e - g.e0] - tv) * (x > 0.f ? 1.f : kSlope);
-                    *reinterpret_cast<float2*>(pair + ((e - g.e0) * g.nh + h) * 2) = make_float2(av, dp);
-                    ds += dp;
+                    float sc[HB], av[HB], dp[HB];
+                    load_scores<HB, false>(g, g.col[e], h0, nhb, sc);
+#pragma unroll
+                    for (int b = 0; b < HB; ++b) {
+                        av[b] = 0.f; dp[b] = 0.f;
+                        if (b < nhb) {
+                            av[b] = att_all[(h0 + b) * g.hs + (e - g.e0)];
+                            dp[b] = av[b] * (dal_all[(h0 + b) * g.hs + (e - g.e0)] - tv[b]) *
+                                    (sc[b] + sd[b] > 0.f ? 1.f : kSlope);
+                            ds[b] += dp[b];
+                        }
+                    }
+                    float* qp = pair + ((e - g.e0) * g.nh + h0) * 2;
+                    if (HB == 2 && VEC) {
+                        *reinterpret_cast<float4*>(qp) = make_float4(av[0], dp[0], av[HB - 1], dp[HB - 1]);
+                    } else {
+#pragma unroll
+                        for (int b = 0; b < HB; ++b)
+                            if (b < nhb) *reinterpret_cast<float2*>(qp + 2 * b) = make_float2(av[b], dp[b]);
+                    }
                 }
             }
-            ds = wave_sum(ds);
-            if (t == 0) stat[sgi] = ds;
+#pragma unroll
+            for (int b = 0; b < HB; ++b) {
+                ds[b] = wave_sum(ds[b]);
+                if (t == 0 && b < nhb) stat_all[(int64_t)(h0 + b) * 2 * q.nsegs + sgi] = ds[b];
+            }
+        }
+    } else {
+        for (int32_t h = 0; h < g.nh; ++h) {
+            float* __restrict__ att = att_all + h * g.hs;
+            if (STEP == 1) {
+                const float f = factor_all[(int64_t)h * q.nsegs + sgi];
+                for (int64_t e = eb + t; e < ee; e += kWave) att[e - g.e0] *= f;
+            } else {
+                const float* __restrict__ dal = dal_all + h * g.hs;
+                float tv = 0.f;
+                for (int64_t e = eb + t; e < ee; e += kWave) tv += att[e - g.e0] * dal[e - g.e0];
+                tv = wave_sum(tv);
+                if (t == 0) stat_all[(int64_t)h * 2 * q.nsegs + sgi] = tv;
+            }
         }
     }
 }
@@ -736,9 +791,12 @@ void launch_gat_attention(const GatRowsHost& h, float* att, float* segwork, hipS
         float* factor = segwork + 2 * q.nsegs * g.nh;
         float* none = nullptr;
         const dim3 gs((unsigned)((q.nsegs + 3) / 4)), gl((unsigned)((q.nlong + 3) / 4)), b(kBlock);
-        hipLaunchKernelGGL((k_gat_segments<0>), gs, b, 0, s, g, q, att, none, stat, (const float*)nullptr, none);
+        const float* nof = nullptr;
+        if (g.nh == 1) hipLaunchKernelGGL((k_gat_segments<0, 1, false>), gs, b, 0, s, g, q, att, none, stat, nof, none);
+        else if (g.nh % 4 == 0) hipLaunchKernelGGL((k_gat_segments<0, 4, true>), gs, b, 0, s, g, q, att, none, stat, nof, none);
+        else hipLaunchKernelGGL((k_gat_segments<0, 4, false>), gs, b, 0, s, g, q, att, none, stat, nof, none);
         hipLaunchKernelGGL((k_gat_combine<0>), gl, b, 0, s, q, g.nh, (const float*)stat, factor, none);
-        hipLaunchKernelGGL((k_gat_segments<1>), gs, b, 0, s, g, q, att, none, none, (const float*)factor, none);
+        hipLaunchKernelGGL((k_gat_segments<1, 1, false>), gs, b, 0, s, g, q, att, none, none, (const float*)factor, none);
     }
 }
 
@@ -751,6 +809,7 @@ void launch_gat_bwd_scalars(const GatRowsHost& h, const float* att, const float*
     if (g.nranges > 0) {
         const dim3 grid((unsigned)((g.nranges + 3) / 4)), b(kBlock);
         if (g.nh == 1) hipLaunchKernelGGL((k_gat_rows<1, 1, false>), grid, b, 0, s, g, a, d, pair, gs_dst_own);
+        else if (g.nh % 4 == 0) hipLaunchKernelGGL((k_gat_rows<1, 4, true>), grid, b, 0, s, g, a, d, pair, gs_dst_own);
         else if (g.nh % 2 == 0) hipLaunchKernelGGL((k_gat_rows<1, 2, true>), grid, b, 0, s, g, a, d, pair, gs_dst_own);
         else hipLaunchKernelGGL((k_gat_rows<1, 2, false>), grid, b, 0, s, g, a, d, pair, gs_dst_own);
     }
@@ -760,9 +819,14 @@ void launch_gat_bwd_scalars(const GatRowsHost& h, const float* att, const float*
         float* factor = segwork + 2 * q.nsegs * g.nh;
         float* none = nullptr;
         const dim3 gs((unsigned)((q.nsegs + 3) / 4)), gl((unsigned)((q.nlong + 3) / 4)), b(kBlock);
-        hipLaunchKernelGGL((k_gat_segments<2>), gs, b, 0, s, g, q, a, d, stat, (const float*)nullptr, none);
+        hipLaunchKernelGGL((k_gat_segments<2, 1, false>), gs, b, 0, s, g, q, a, d, stat, (const float*)nullptr, none);
         hipLaunchKernelGGL((k_gat_combine<2>), gl, b, 0, s, q, g.nh, (const float*)stat, factor, none);
-        hipLaunchKernelGGL((k_gat_segments<3>), gs, b, 0, s, g, q, a, d, stat, (const float*)factor, pair);
+        if (g.nh == 1)
+            hipLaunchKernelGGL((k_gat_segments<3, 1, false>), gs, b, 0, s, g, q, a, d, stat, (const float*)factor, pair);
+        else if (g.nh % 2 == 0)
+            hipLaunchKernelGGL((k_gat_segments<3, 2, true>), gs, b, 0, s, g, q, a, d, stat, (const float*)factor, pair);
+        else
+            hipLaunchKernelGGL((k_gat_segments<3, 2, false>), gs, b, 0, s, g, q, a, d, stat, (const float*)factor, pair);
         hipLaunchKernelGGL((k_gat_combine<3>), gl, b, 0, s, q, g.nh, (const float*)stat, none, gs_dst_own);
     }
 }
