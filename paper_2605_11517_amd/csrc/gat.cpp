@@ -21,15 +21,24 @@ namespace {
 // One head of a layer on one partition.  With one head: f = d_l, fp = the padded row width, and
 // every offset below is zero.  With several, head j is a layer of its own on columns
 // [j f, (j + 1) f) of W, of the attention vectors, of the bias and of the output, with its own
-// arrays of H and grad H (fp floats per vertex) and of attention weights and edge-wise products
-// (`hs` floats per head); the scores of a vertex lie side by side, nh floats per vertex, so that
-// the row-wise passes fetch a neighbour's scores once for all heads (they run all heads in one
-// launch; the pointers below then are head 0's).
+// attention weights and edge-wise products (`hs` floats per head).  H, grad H and the staged rows
+// of the heads lie
+//   side by side  (f a multiple of 4: rows of d_l floats, head j at column j f; the layer's
+//                  contractions, its gather and its row-wise kernels then run once, on whole
+//                  rows, and only the aggregations and the edge-wise products go head by head, on
+//                  a column block each), or
+//   head after head  (otherwise: an array of fp = f rounded up to 4 floats per vertex for
+//                  every head, every step head by head).
+// Either way a head's rows are `ldh` floats apart.  The scores of a vertex lie side by side, nh
+// floats per vertex, so that the row-wise passes fetch a neighbour's scores once for all heads
+// (they run all heads in one launch; the score pointers below then are head 0's).
 struct GatView {
     int64_t r0, np, nb, e0, n, hs;
-    int32_t din, dout, nh, f, fp;
+    int32_t din, dout, nh, f, fp, ldh;
+    bool side;                  // heads side by side
     float *H, *gH, *ssrc, *sdst, *gssrc, *gsdst, *bs, *att, *dal, *twatt, *pair, *stg;
     const float *W, *a_src, *a_dst;
+    int64_t own() const { return r0 * ldh; }     // offset of the partition's first row in H / grad H
 };
 
 GatView view(gnn_ctx* c, int32_t layer, int32_t p, int32_t h)
@@ -46,16 +55,19 @@ GatView view(gnn_ctx* c, int32_t layer, int32_t p, int32_t h)
     v.nh = c->nheads(layer);
     v.f = c->head_cols(layer);
     v.fp = c->head_padded(layer);
+    v.side = v.nh > 1 && v.fp == v.f;
+    v.ldh = v.side ? v.dout : v.fp;
     char* sc = c->scratch;
-    v.H = (float*)c->hbuf + (int64_t)h * v.n * v.fp;
-    v.gH = (float*)c->ghbuf + (int64_t)h * v.n * v.fp;
+    const int64_t hoff = v.side ? (int64_t)h * v.f : (int64_t)h * v.n * v.fp;
+    v.H = (float*)c->hbuf + hoff;
+    v.gH = (float*)c->ghbuf + hoff;
     // scores: element (vertex r, head h) at [r nh + h]
     v.ssrc = (float*)(sc + c->ws.ssrc) + h;
     v.sdst = (float*)(sc + c->ws.sdst) + h;
     v.gssrc = (float*)(sc + c->ws.gssrc) + h;
     v.gsdst = (float*)(sc + c->ws.gsdst) + h;
     v.bs = (float*)(sc + c->ws.bs) + h;
-    v.stg = (float*)c->staging + (int64_t)h * v.nb * v.fp;
+    v.stg = (float*)c->staging + (v.side ? (int64_t)h * v.f : (int64_t)h * v.nb * v.fp);
     v.hs = M.stats.max_nnz;
     v.att = (float*)(sc + c->ws.att) + (int64_t)h * v.hs;
     v.dal = (float*)(sc + c->ws.dal) + (int64_t)h * v.hs;
@@ -88,36 +100,41 @@ GatRowsHost rows_of(gnn_ctx* c, const GatView& v, int32_t p)
 void gat_transform_fwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
 {
     const int32_t nh = c->nheads(layer);
-    for (int32_t h = 0; h < nh; ++h) {
+    const GatView v0 = view(c, layer, p, 0);
+    const float* in_own = (const float*)c->layer_input(layer, v0.r0);
+    // H_p = A_p^{l-1} W: one contraction for whole rows, or one per head
+    const int32_t steps = v0.side ? 1 : nh;
+    for (int32_t h = 0; h < steps; ++h) {
         const GatView v = view(c, layer, p, h);
-        float* Hp = v.H + v.r0 * v.fp;
+        float* Hp = v.H + v.own();
         if (v.fp != v.f) {
             Timed t(c, s, GNN_K_OTHER);
             launch_fill_zero(Hp, v.np * (int64_t)v.fp * 4, s);
         }
-        {
-            Timed t(c, s, GNN_K_GEMM_FWD);
-            GemmSeg seg;
-            seg.a = (const float*)c->layer_input(layer, v.r0); seg.lda = v.din;
-            seg.b = v.W; seg.ldb = v.dout; seg.k = v.din;
-            launch_gemm_nn(&seg, 1, Hp, v.fp, v.np, v.f, GemmEpilogue{}, s);
-        }
-        Timed t(c, s, GNN_K_OTHER);
-        launch_gat_scores(Hp, v.fp, v.f, v.np, v.a_src, v.a_dst, v.ssrc + v.r0 * v.nh, v.sdst + v.r0 * v.nh, v.nh, s);
+        Timed t(c, s, GNN_K_GEMM_FWD);
+        GemmSeg seg;
+        seg.a = in_own; seg.lda = v.din;
+        seg.b = v.W; seg.ldb = v.dout; seg.k = v.din;
+        launch_gemm_nn(&seg, 1, Hp, v.ldh, v.np, v.side ? v.dout : v.f, GemmEpilogue{}, s);
     }
+    Timed t(c, s, GNN_K_OTHER);
+    launch_gat_scores(v0.H + v0.own(), v0.ldh, v0.f, v0.np, v0.a_src, v0.a_dst, v0.ssrc + v0.r0 * nh,
+                      v0.sdst + v0.r0 * nh, nh, v0.side ? (int64_t)v0.f : v0.n * (int64_t)v0.fp, s);
 }
 
-// rows of H and scores s_src of the boundary vertices of p, head by head
+// rows of H and scores s_src of the boundary vertices of p
 void gat_gather(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
 {
     const int32_t nh = c->nheads(layer);
     const int32_t* bnd = c->D.bnd + c->M.boff[(size_t)p];
+    const GatView v0 = view(c, layer, p, 0);
     Timed t(c, s, GNN_K_GATHER);
-    for (int32_t h = 0; h < nh; ++h) {
+    const int32_t steps = v0.side ? 1 : nh;
+    for (int32_t h = 0; h < steps; ++h) {
         const GatView v = view(c, layer, p, h);
-        launch_gather_rows(v.H, bnd, v.stg, v.nb, (int64_t)v.fp * 4, s);
-        if (h == 0) launch_gather_rows(v.ssrc, bnd, v.bs, v.nb, (int64_t)nh * 4, s);   // all heads' scores
+        launch_gather_rows(v.H, bnd, v.stg, v.nb, (int64_t)v.ldh * 4, s);
     }
+    launch_gather_rows(v0.ssrc, bnd, v0.bs, v0.nb, (int64_t)nh * 4, s);   // all heads' scores
 }
 
 void gat_layer_fwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
@@ -125,29 +142,39 @@ void gat_layer_fwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
     const int32_t nh = c->nheads(layer);
     float* Z = (float*)(c->scratch + c->ws.z);
     float* segpart = (float*)(c->scratch + c->ws.segpart);
+    const GatView v0 = view(c, layer, p, 0);
+    const GatRowsHost rows = rows_of(c, v0, p);
     {
         // attention weights of every head
-        const GatView v = view(c, layer, p, 0);
         Timed t(c, s, GNN_K_OTHER);
-        launch_gat_attention(rows_of(c, v, p), v.att, segpart, s);
+        launch_gat_attention(rows, v0.att, segpart, s);
     }
+    const float* bias = c->has_bias ? (const float*)c->w[(size_t)3 * (layer - 1) + 2] : nullptr;
+    float* out = (float*)c->act[(size_t)layer - 1] + v0.r0 * v0.dout;
+    const int relu = layer < c->L ? 1 : 0;
     for (int32_t h = 0; h < nh; ++h) {
         const GatView v = view(c, layer, p, h);
-        const GatRowsHost rows = rows_of(c, v, p);
+        // Z rows like the rows of H: the head's column block, or an array of its own
+        float* Zh = Z + (v.side ? (int64_t)h * v.f : 0);
         {
             Timed t(c, s, GNN_K_SPMM);
-            launch_spmm(rows.rp, rows.col, v.att - v.e0, nullptr, v.H + v.r0 * v.fp, v.np, v.stg, Z, v.np, v.fp,
-                        0, 0, rows.items, segpart, 1, SpmmScatter{}, s);
+            launch_spmm(rows.rp, rows.col, v.att - v.e0, nullptr, v.H + v.own(), v.np, v.stg, Zh, v.np, v.fp,
+                        0, 0, rows.items, segpart, 1, SpmmScatter{}, s, v.ldh);
         }
         if (rows.items.nlong > 0) {
             Timed t(c, s, GNN_K_SPMM_REDUCE);
-            launch_spmm_reduce(nullptr, Z, v.fp, 0, rows.items, segpart, SpmmScatter{}, s);
+            launch_spmm_reduce(nullptr, Zh, v.fp, 0, rows.items, segpart, SpmmScatter{}, s, v.ldh);
         }
-        // the head's columns of the output rows
-        float* out = (float*)c->act[(size_t)layer - 1] + v.r0 * v.dout + (int64_t)h * v.f;
-        const float* bias = c->has_bias ? (const float*)c->w[(size_t)3 * (layer - 1) + 2] + (int64_t)h * v.f : nullptr;
+        if (!v.side) {
+            // the head's columns of the output rows
+            Timed t(c, s, GNN_K_GEMM_FWD);
+            launch_add_padded(out + (int64_t)h * v.f, Z, v.np, v.f, v.fp, bias ? bias + (int64_t)h * v.f : nullptr, 0,
+                              relu, s, v.dout);
+        }
+    }
+    if (v0.side) {
         Timed t(c, s, GNN_K_GEMM_FWD);
-        launch_add_padded(out, Z, v.np, v.f, v.fp, bias, 0, layer < c->L ? 1 : 0, s, v.dout);
+        launch_add_padded(out, Z, v0.np, v0.dout, v0.dout, bias, 0, relu, s);
     }
 }
 
@@ -193,20 +220,24 @@ void gat_layer_bwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
         Timed t(c, s, GNN_K_OTHER);
         launch_gat_attention(rows, v0.att, segpart, s);
     }
-    // the head's columns of dY as rows of fp floats, head after head (np fp floats each)
+    // The head's columns of dY with rows ldh floats apart: dY itself when the heads lie side by
+    // side (or there is one head of unpadded width), else copies of fp floats per row, head after
+    // head (np fp floats each).
     float* pad = (float*)(c->scratch + c->ws.dz);
-    const bool padded = nh > 1 || v0.fp != v0.f;
+    const bool copy = !v0.side && (nh > 1 || v0.fp != v0.f);
+    auto dy_of = [&](const GatView& v, int32_t h) -> const float* {
+        if (copy) return pad + (int64_t)h * v.np * v.fp;
+        return dY + (v.side ? (int64_t)h * v.f : 0);
+    };
     for (int32_t h = 0; h < nh; ++h) {
         const GatView v = view(c, layer, p, h);
-        const float* dYp = dY;
-        if (padded) {
+        if (copy) {
             Timed t(c, s, GNN_K_OTHER);
-            float* ph = pad + (int64_t)h * v.np * v.fp;
-            launch_pad_rows(ph, dY + (int64_t)h * v.f, v.np, v.f, v.fp, s, v.dout);
-            dYp = ph;
+            launch_pad_rows(pad + (int64_t)h * v.np * v.fp, dY + (int64_t)h * v.f, v.np, v.f, v.fp, s, v.dout);
         }
         Timed t(c, s, GNN_K_SPMM);      // edge-wise products: one source row read per entry
-        launch_gat_dots(rows.rp, rows.col, v.e0, v.np, v.H + v.r0 * v.fp, v.stg, dYp, v.fp, v.dal, rows.items, s);
+        launch_gat_dots(rows.rp, rows.col, v.e0, v.np, v.H + v.own(), v.stg, dy_of(v, h), v.fp, v.ldh, v.dal,
+                        rows.items, s);
     }
     {
         Timed t(c, s, GNN_K_OTHER);     // every head
@@ -216,19 +247,18 @@ void gat_layer_bwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
     }
     for (int32_t h = 0; h < nh; ++h) {
         const GatView v = view(c, layer, p, h);
-        const float* dYp = padded ? pad + (int64_t)h * v.np * v.fp : dY;
         SpmmScatter sc;
         sc.n_own = v.np;
         sc.base_row = v.r0;
         sc.idx = bnd;
         {
             Timed t(c, s, GNN_K_SPMM_T);
-            launch_spmm(c->D.trp + t0, c->D.tcol, v.twatt - v.e0, nullptr, dYp, v.np, nullptr, v.gH, v.np + v.nb, v.fp,
-                        0, 0, titems, segpart, 0, sc, s);
+            launch_spmm(c->D.trp + t0, c->D.tcol, v.twatt - v.e0, nullptr, dy_of(v, h), v.np, nullptr, v.gH,
+                        v.np + v.nb, v.fp, 0, 0, titems, segpart, 0, sc, s, v.ldh);
         }
         if (titems.nlong > 0) {
             Timed t(c, s, GNN_K_SPMM_REDUCE);
-            launch_spmm_reduce(nullptr, v.gH, v.fp, 0, titems, segpart, sc, s);
+            launch_spmm_reduce(nullptr, v.gH, v.fp, 0, titems, segpart, sc, s, v.ldh);
         }
     }
 }
@@ -238,47 +268,58 @@ void gat_transform_bwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
     const int32_t nh = c->nheads(layer);
     float* part = (float*)(c->scratch + c->ws.colpart);
     float* ga = c->gw[(size_t)3 * (layer - 1) + 1];       // grad a_src (d_l floats), then grad a_dst
-    for (int32_t h = 0; h < nh; ++h) {
-        const GatView v = view(c, layer, p, h);
-        float* gHp = v.gH + v.r0 * v.fp;
-        const float* Hp = v.H + v.r0 * v.fp;
+    float* gW = c->gw[(size_t)3 * (layer - 1)];
+    float* splitk = (float*)(c->scratch + c->ws.partial);
+    const GatView v0 = view(c, layer, p, 0);
+    const float* in_own = (const float*)c->layer_input(layer, v0.r0);
+    float* gprev = layer >= 2 ? c->gact[(size_t)layer - 2] + v0.r0 * v0.din : nullptr;
+    if (nh == 1 || v0.side) {
+        // whole rows: one rank-one update, one weight gradient, one input gradient
+        float* gHp = v0.gH + v0.own();
         {
             Timed t(c, s, GNN_K_OTHER);
-            launch_gat_rank1(gHp, Hp, v.fp, v.f, v.np, v.gssrc + v.r0 * nh, v.gsdst + v.r0 * nh, nh, v.a_src, v.a_dst,
-                             part, s);
-            if (nh == 1) {
-                launch_colsum_finish(part, (v.np + 255) / 256, 2 * v.dout, ga, s);
-            } else {
-                launch_colsum_finish(part, (v.np + 255) / 256, v.f, ga + (int64_t)h * v.f, s, 2 * v.f);
-                launch_colsum_finish(part + v.f, (v.np + 255) / 256, v.f, ga + v.dout + (int64_t)h * v.f, s, 2 * v.f);
-            }
+            launch_gat_rank1(gHp, v0.H + v0.own(), v0.ldh, v0.dout, v0.np, v0.gssrc + v0.r0 * nh, v0.gsdst + v0.r0 * nh,
+                             nh, v0.f, v0.a_src, v0.a_dst, part, s);
+            launch_colsum_finish(part, (v0.np + 255) / 256, 2 * v0.dout, ga, s);
         }
-        const float* in_own = (const float*)c->layer_input(layer, v.r0);
-        Timed t(c, s, GNN_K_GEMM_DW);
-        launch_gemm_tn(in_own, v.din, gHp, v.fp, c->gw[(size_t)3 * (layer - 1)] + (int64_t)h * v.f, v.dout, v.din,
-                       v.f, v.np, (float*)(c->scratch + c->ws.partial), s);
+        {
+            Timed t(c, s, GNN_K_GEMM_DW);
+            launch_gemm_tn(in_own, v0.din, gHp, v0.ldh, gW, v0.dout, v0.din, v0.dout, v0.np, splitk, s);
+        }
+        if (gprev) {
+            Timed t(c, s, GNN_K_GEMM_DZ);   // the only term of grad A^{l-1}_p: written, not accumulated
+            launch_gemm_nt(gHp, v0.ldh, v0.W, v0.dout, gprev, v0.din, v0.np, v0.din, v0.dout, GemmEpilogue{}, s);
+        }
+        return;
     }
-    if (layer >= 2) {
+    for (int32_t h = 0; h < nh; ++h) {
+        const GatView v = view(c, layer, p, h);
+        float* gHp = v.gH + v.own();
+        {
+            Timed t(c, s, GNN_K_OTHER);
+            launch_gat_rank1(gHp, v.H + v.own(), v.ldh, v.f, v.np, v.gssrc + v.r0 * nh, v.gsdst + v.r0 * nh, nh, v.f,
+                             v.a_src, v.a_dst, part, s);
+            launch_colsum_finish(part, (v.np + 255) / 256, v.f, ga + (int64_t)h * v.f, s, 2 * v.f);
+            launch_colsum_finish(part + v.f, (v.np + 255) / 256, v.f, ga + v.dout + (int64_t)h * v.f, s, 2 * v.f);
+        }
+        Timed t(c, s, GNN_K_GEMM_DW);
+        launch_gemm_tn(in_own, v.din, gHp, v.ldh, gW + (int64_t)h * v.f, v.dout, v.din, v.f, v.np, splitk, s);
+    }
+    if (gprev) {
         // grad A^{l-1}_p = sum over heads of grad H_p W^T on the head's columns: written by the
         // first contraction (two heads at a time), accumulated by the others
         Timed t(c, s, GNN_K_GEMM_DZ);
-        const GatView v = view(c, layer, p, 0);
-        float* out = c->gact[(size_t)layer - 2] + v.r0 * v.din;
-        if (nh == 1) {
-            launch_gemm_nt(v.gH + v.r0 * v.fp, v.fp, v.W, v.dout, out, v.din, v.np, v.din, v.dout, GemmEpilogue{}, s);
-        } else {
-            for (int32_t h0 = 0; h0 < nh; h0 += 2) {
-                GemmSeg segs[2];
-                const int nseg = nh - h0 < 2 ? 1 : 2;
-                for (int i = 0; i < nseg; ++i) {
-                    const GatView vh = view(c, layer, p, h0 + i);
-                    segs[i].a = vh.gH + vh.r0 * vh.fp; segs[i].lda = vh.fp;
-                    segs[i].b = vh.W; segs[i].ldb = vh.dout; segs[i].k = vh.f;
-                }
-                GemmEpilogue ep;
-                ep.accumulate = h0 > 0 ? 1 : 0;
-                launch_gemm_nt2(segs, nseg, out, v.din, v.np, v.din, ep, s);
+        for (int32_t h0 = 0; h0 < nh; h0 += 2) {
+            GemmSeg segs[2];
+            const int nseg = nh - h0 < 2 ? 1 : 2;
+            for (int i = 0; i < nseg; ++i) {
+                const GatView vh = view(c, layer, p, h0 + i);
+                segs[i].a = vh.gH + vh.own(); segs[i].lda = vh.ldh;
+                segs[i].b = vh.W; segs[i].ldb = vh.dout; segs[i].k = vh.f;
             }
+            GemmEpilogue ep;
+            ep.accumulate = h0 > 0 ? 1 : 0;
+            launch_gemm_nt2(segs, nseg, gprev, v0.din, v0.np, v0.din, ep, s);
         }
     }
 }

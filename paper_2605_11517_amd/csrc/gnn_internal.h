@@ -144,12 +144,13 @@ struct SpmmScatter {
     int relu = 0;
 };
 // a_rows / b_rows hold fp32 (in_bf16 = 0) or bfloat16 rows; out is fp32 or bfloat16; the sums
-// and `partial` are always fp32.
+// and `partial` are always fp32.  ld (0: d): the rows of a_rows, b_rows, out and partial start ld
+// elements apart and the call works on d of their columns (a column block of wider arrays).
 void launch_spmm(const int64_t* rp, const int32_t* col, const float* w, const float* rowscale,
                  const void* a_rows, int64_t n_a, const void* b_rows, void* out, int64_t nrows,
                  int32_t d, int in_bf16, int out_bf16, const SpmmItems& items, float* partial,
                  int column_slices /* allow the XCD column-sliced kernel */, const SpmmScatter& sc,
-                 hipStream_t s);
+                 hipStream_t s, int32_t ld = 0);
 // Aggregation fused with the transform, fp32: y[r,:] = act(Z[r,:] W (+ xself[r,:] Ws) + bias) with
 // Z as launch_spmm would compute it, kept in LDS.  zlong: n_a x din floats of scratch for the
 // rows that are cut into segments.  Only when spmm_gemm_fused_ok() (d_in in 36..128, a multiple
@@ -166,7 +167,8 @@ void launch_spmm_gemm_fused(const int64_t* rp, const int32_t* col, const float* 
                             int32_t dout, int stage, hipStream_t s);
 // second step of the aggregation: combines the segment partial sums of the long rows
 void launch_spmm_reduce(const float* rowscale, void* out, int32_t d, int out_bf16,
-                        const SpmmItems& items, float* partial, const SpmmScatter& sc, hipStream_t s);
+                        const SpmmItems& items, float* partial, const SpmmScatter& sc, hipStream_t s,
+                        int32_t ld = 0);
 
 // dst[map(i),:] += src[i,:] with map(i) = base_row + i for i < n_own, idx[i - n_own] otherwise.
 void launch_scatter_add(const float* src, int64_t nrows, int64_t n_own, int64_t base_row,
@@ -288,15 +290,16 @@ struct GatRowsHost {
     int64_t hs = 0;
     SpmmItems items;
 };
-// one head: ssrc[r nh] = H[r, :f] . a_src, sdst[r nh] = H[r, :f] . a_dst for `rows` rows
+// every head h < nh: ssrc[r nh + h] = H_h[r, :f] . a_src[h f ..], sdst[r nh + h] = H_h[r, :f] . a_dst[h f ..]
+// for `rows` rows, H_h = H + h head_off with rows ld floats apart
 void launch_gat_scores(const float* H, int32_t ld, int32_t f, int64_t rows, const float* a_src,
-                       const float* a_dst, float* ssrc, float* sdst, int32_t nh, hipStream_t s);
+                       const float* a_dst, float* ssrc, float* sdst, int32_t nh, int64_t head_off, hipStream_t s);
 // att[e - e0] = softmax over each row of LeakyReLU_0.2(s_src(col e) + s_dst(row))
 // segwork: 3 floats per head and segment of the partition's long rows (scratch of the segment-parallel passes)
 void launch_gat_attention(const GatRowsHost& h, float* att, float* segwork, hipStream_t s);
-// dal[e - e0] = dy[row,:] . src(col e)[:]  (rows of width ld, a multiple of 4)
+// dal[e - e0] = dy[row, :d] . src(col e)[:d]  (rows ld floats apart; d and ld multiples of 4)
 void launch_gat_dots(const int64_t* rp, const int32_t* col, int64_t e0, int64_t n_own, const float* a_rows,
-                     const float* b_rows, const float* dy, int32_t ld, float* dal, const SpmmItems& items,
+                     const float* b_rows, const float* dy, int32_t d, int32_t ld, float* dal, const SpmmItems& items,
                      hipStream_t s);
 // gradient of the pre-activation scores (through softmax and LeakyReLU) from att and dal, every
 // head: pair[((e - e0) nh + h) 2 + {0, 1}] = att, dpre (an entry's values of all heads side by
@@ -308,13 +311,14 @@ void launch_gat_bwd_scalars(const GatRowsHost& h, const float* att, const float*
 void launch_gat_transposed(const int64_t* trp, const int32_t* tperm, int64_t e0, int64_t n_own,
                            int64_t base_row, const int32_t* bnd, const SpmmItems& items, const float* pair,
                            float* tw_att, float* gs_src, int32_t nh, int64_t hs, hipStream_t s);
-// one head: gH += gs_src a_src^T + gs_dst a_dst^T over `rows` rows (the head's scores nh floats
-// apart); partial column sums of gs_src H and gs_dst H (2 f floats per block of 256 rows) for
-// the gradients of the attention vectors
+// gH[r, j] += gs_src[r nh + j / fh] a_src[j] + gs_dst[r nh + j / fh] a_dst[j] over `rows` rows and f
+// columns (column j belongs to head j / fh of the score arrays; fh = f and offset pointers: one
+// head); partial column sums of gs_src H and gs_dst H (2 f floats per block of 256 rows) for the
+// gradients of the attention vectors
 int64_t gat_rank1_partial_floats(int64_t rows, int32_t f);
 void launch_gat_rank1(float* gH, const float* H, int32_t ld, int32_t f, int64_t rows, const float* gs_src,
-                      const float* gs_dst, int32_t nh, const float* a_src, const float* a_dst, float* partial,
-                      hipStream_t s);
+                      const float* gs_dst, int32_t nh, int32_t fh, const float* a_src, const float* a_dst,
+                      float* partial, hipStream_t s);
 // out[c] += sum over b < nblocks of partial[b * ldp + c] for c < d (ldp = 0: rows of d floats)
 void launch_colsum_finish(const float* partial, int64_t nblocks, int32_t d, float* out, hipStream_t s,
                           int32_t ldp = 0);

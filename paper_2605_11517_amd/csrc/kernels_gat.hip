@@ -69,16 +69,24 @@ struct GatRows {
 
 __device__ inline float lrelu(float x) { return x > 0.f ? x : kSlope * x; }
 
-// s_src[r nh] = H[r,:] . a_src, s_dst[r nh] = H[r,:] . a_dst; one wavefront per row
+// head h = blockIdx.y: s_src[r nh + h] = H_h[r,:] . a_src_h, s_dst[r nh + h] = H_h[r,:] . a_dst_h with
+// H_h = H + h head_off (rows ld floats apart) and the head's f entries of the attention vectors;
+// one wavefront per row and head
 __global__ __launch_bounds__(kBlock) void k_gat_scores(const float* __restrict__ H, int32_t ld, int32_t f,
                                                        int64_t rows, const float* __restrict__ a_src,
                                                        const float* __restrict__ a_dst,
                                                        float* __restrict__ ssrc, float* __restrict__ sdst,
-                                                       int32_t nh)
+                                                       int32_t nh, int64_t head_off)
 {
     const int lane = threadIdx.x % kWave;
     const int64_t r = (int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;
     if (r >= rows) return;
+    const int32_t hd = blockIdx.y;
+    H += hd * head_off;
+    a_src += hd * f;
+    a_dst += hd * f;
+    ssrc += hd;
+    sdst += hd;
     float s1 = 0.f, s2 = 0.f;
     for (int j = lane; j < f; j += kWave) {
         const float h = H[r * ld + j];
@@ -592,6 +600,7 @@ struct GatDotArgs {
     const float* b_rows;
     const float* dy;            // [n_own, ld]
     int32_t ld;                 // row stride of H, staging and dy (multiple of 4)
+    int32_t d;                  // columns of those rows the products run over (multiple of 4)
     float* dal;
     SpmmItems it;
 };
@@ -606,7 +615,7 @@ __device__ inline void dot_entries(const GatDotArgs& g, int32_t row, int64_t eb,
 #pragma unroll
     for (int v = 0; v < NV; ++v) {
         const int c = (v * G + gl) * 4;
-        cv[v] = c < g.ld ? c : -1;
+        cv[v] = c < g.d ? c : -1;
         y[v] = cv[v] >= 0 ? *reinterpret_cast<const float4*>(g.dy + (int64_t)row * g.ld + c)
                           : make_float4(0.f, 0.f, 0.f, 0.f);
         if (cv[v] < 0) cv[v] = 0;
@@ -682,7 +691,7 @@ __global__ __launch_bounds__(kBlock) void k_gat_rank1(float* __restrict__ gH, co
                                                       const float* __restrict__ gs_dst,
                                                       const float* __restrict__ a_src,
                                                       const float* __restrict__ a_dst,
-                                                      float* __restrict__ partial, int32_t nh)
+                                                      float* __restrict__ partial, int32_t nh, int32_t fh)
 {
     const int64_t r0 = (int64_t)blockIdx.x * 256;
     const int64_t r1 = r0 + 256 < rows ? r0 + 256 : rows;
@@ -690,7 +699,7 @@ __global__ __launch_bounds__(kBlock) void k_gat_rank1(float* __restrict__ gH, co
         const float as = a_src[j], ad = a_dst[j];
         float p1 = 0.f, p2 = 0.f;
         for (int64_t r = r0; r < r1; ++r) {
-            const float gs = gs_src[r * nh], gd = gs_dst[r * nh];
+            const float gs = gs_src[r * nh + j / fh], gd = gs_dst[r * nh + j / fh];
             const float h = H[r * ld + j];
             gH[r * ld + j] += gs * as + gd * ad;
             p1 += gs * h;
@@ -711,7 +720,7 @@ __global__ __launch_bounds__(kBlock) void k_gat_rank1_narrow(float* __restrict__
                                                              const float* __restrict__ gs_dst,
                                                              const float* __restrict__ a_src,
                                                              const float* __restrict__ a_dst,
-                                                             float* __restrict__ partial, int32_t nh)
+                                                             float* __restrict__ partial, int32_t nh, int32_t fh)
 {
     constexpr int RG = kBlock / CW;
     __shared__ float sm[RG][CW][2];
@@ -722,7 +731,7 @@ __global__ __launch_bounds__(kBlock) void k_gat_rank1_narrow(float* __restrict__
     if (j < f) {
         const float as = a_src[j], ad = a_dst[j];
         for (int64_t r = r0 + rgp; r < r1; r += RG) {
-            const float gs = gs_src[r * nh], gd = gs_dst[r * nh];
+            const float gs = gs_src[r * nh + j / fh], gd = gs_dst[r * nh + j / fh];
             const float h = H[r * ld + j];
             gH[r * ld + j] += gs * as + gd * ad;
             p1 += gs * h;
@@ -745,12 +754,12 @@ __global__ __launch_bounds__(kBlock) void k_gat_rank1_narrow(float* __restrict__
 }  // namespace
 
 void launch_gat_scores(const float* H, int32_t ld, int32_t f, int64_t rows, const float* a_src,
-                       const float* a_dst, float* ssrc, float* sdst, int32_t nh, hipStream_t s)
+                       const float* a_dst, float* ssrc, float* sdst, int32_t nh, int64_t head_off, hipStream_t s)
 {
     if (rows <= 0) return;
     const int64_t blocks = (rows + kBlock / kWave - 1) / (kBlock / kWave);
-    hipLaunchKernelGGL(k_gat_scores, dim3((unsigned)blocks), dim3(kBlock), 0, s, H, ld, f, rows, a_src, a_dst,
-                       ssrc, sdst, nh);
+    hipLaunchKernelGGL(k_gat_scores, dim3((unsigned)blocks, (unsigned)nh), dim3(kBlock), 0, s, H, ld, f, rows, a_src,
+                       a_dst, ssrc, sdst, nh, head_off);
 }
 
 static GatRows make_rows(const GatRowsHost& h)
@@ -851,16 +860,16 @@ void launch_gat_transposed(const int64_t* trp, const int32_t* tperm, int64_t e0,
 }
 
 void launch_gat_dots(const int64_t* rp, const int32_t* col, int64_t e0, int64_t n_own, const float* a_rows,
-                     const float* b_rows, const float* dy, int32_t ld, float* dal, const SpmmItems& items,
+                     const float* b_rows, const float* dy, int32_t d, int32_t ld, float* dal, const SpmmItems& items,
                      hipStream_t s)
 {
     const int64_t nitems = items.nsegs + items.nranges;
     if (nitems <= 0) return;
     GatDotArgs g;
     g.rp = rp; g.col = col; g.e0 = e0; g.n_own = n_own; g.a_rows = a_rows; g.b_rows = b_rows; g.dy = dy;
-    g.ld = ld; g.dal = dal; g.it = items;
+    g.ld = ld; g.d = d; g.dal = dal; g.it = items;
     const dim3 grid((unsigned)((nitems + 3) / 4)), block(kBlock);
-    const int vecs = ld / 4;
+    const int vecs = d / 4;
     if (vecs <= 4) hipLaunchKernelGGL((k_gat_dots<4, 1>), grid, block, 0, s, g);
     else if (vecs <= 8) hipLaunchKernelGGL((k_gat_dots<8, 1>), grid, block, 0, s, g);
     else if (vecs <= 16) hipLaunchKernelGGL((k_gat_dots<16, 1>), grid, block, 0, s, g);
@@ -875,22 +884,22 @@ void launch_gat_dots(const int64_t* rp, const int32_t* col, int64_t e0, int64_t 
 int64_t gat_rank1_partial_floats(int64_t rows, int32_t f) { return ((rows + 255) / 256) * 2 * (int64_t)f; }
 
 void launch_gat_rank1(float* gH, const float* H, int32_t ld, int32_t f, int64_t rows, const float* gs_src,
-                      const float* gs_dst, int32_t nh, const float* a_src, const float* a_dst, float* partial,
-                      hipStream_t s)
+                      const float* gs_dst, int32_t nh, int32_t fh, const float* a_src, const float* a_dst,
+                      float* partial, hipStream_t s)
 {
     if (rows <= 0) return;
     const dim3 grid((unsigned)((rows + 255) / 256)), b(kBlock);
     if (f <= 32)
         hipLaunchKernelGGL((k_gat_rank1_narrow<32>), grid, b, 0, s, gH, H, ld, f, rows, gs_src, gs_dst, a_src, a_dst,
-                           partial, nh);
+                           partial, nh, fh);
     else if (f <= 64)
         hipLaunchKernelGGL((k_gat_rank1_narrow<64>), grid, b, 0, s, gH, H, ld, f, rows, gs_src, gs_dst, a_src, a_dst,
-                           partial, nh);
+                           partial, nh, fh);
     else if (f <= 128)
         hipLaunchKernelGGL((k_gat_rank1_narrow<128>), grid, b, 0, s, gH, H, ld, f, rows, gs_src, gs_dst, a_src, a_dst,
-                           partial, nh);
+                           partial, nh, fh);
     else
-        hipLaunchKernelGGL(k_gat_rank1, grid, b, 0, s, gH, H, ld, f, rows, gs_src, gs_dst, a_src, a_dst, partial, nh);
+        hipLaunchKernelGGL(k_gat_rank1, grid, b, 0, s, gH, H, ld, f, rows, gs_src, gs_dst, a_src, a_dst, partial, nh, fh);
 }
 
 }  // namespace gnnmi

@@ -1065,7 +1065,7 @@ template <typename TIn, typename TOut>
 void spmm_typed(const int64_t* rp, const int32_t* col, const float* w, const float* rowscale,
                 const void* a_rows, int64_t n_a, const void* b_rows, void* out, int32_t d,
                 const SpmmItems& items, float* partial, bool slices, const SpmmScatter& sc,
-                hipStream_t s)
+                hipStream_t s, int32_t ld)
 {
     constexpr int EPV = Elem<TIn>::EPV;
     const int wpb = kBlock / kWave;
@@ -1092,7 +1092,7 @@ void spmm_typed(const int64_t* rp, const int32_t* col, const float* w, const flo
         if (ns > 1 && (G == 16 || G == 32) && blocks * ns < ((int64_t)1 << 31) && n_items > 0) {
             SpmmArgs g;
             g.rp = rp; g.col = col; g.w = w; g.rowscale = rowscale;
-            g.a_rows = a_rows; g.n_a = n_a; g.b_rows = b_rows; g.out = out; g.d = d; g.ld = d;
+            g.a_rows = a_rows; g.n_a = n_a; g.b_rows = b_rows; g.out = out; g.d = d; g.ld = ld;
             g.it = items; g.partial = partial;
             g.map_n_own = -1; g.map_base = 0; g.map_idx = nullptr; g.map_first = nullptr;
             g.bias = sc.bias; g.relu = sc.relu;
@@ -1105,7 +1105,7 @@ void spmm_typed(const int64_t* rp, const int32_t* col, const float* w, const flo
             return;
         }
     }
-    const bool vec = (d % EPV == 0) && (d % Elem<TOut>::EPV == 0);
+    const bool vec = (d % EPV == 0) && (d % Elem<TOut>::EPV == 0) && (ld % EPV == 0) && (ld % Elem<TOut>::EPV == 0);
     // Narrow rows (at most 512 bytes): the cost is latency per row, not bytes, above all in the
     // transposed operator whose rows have a handful of entries.  The slot-per-item kernel without
     // slicing works on 64 / G rows per wavefront at once instead of one after the other.
@@ -1121,7 +1121,7 @@ void spmm_typed(const int64_t* rp, const int32_t* col, const float* w, const flo
     // 18.4 ms at 12; forward 3 % at 17 entries per row, nothing at 55.  `few`: one source array of
     // fewer than 2^32 elements, 32-bit offsets; `few2`: 64-bit addresses.
     const bool short_rows = items.avg_len > 0.f && items.avg_len < short_rows_max();
-    const bool few = short_rows && b_rows == nullptr && n_a * (int64_t)d < ((int64_t)1 << 32);
+    const bool few = short_rows && b_rows == nullptr && n_a * (int64_t)ld < ((int64_t)1 << 32);
     const bool few2 = short_rows && !few;
     if (use_narrow && vec && (few || few2) && nvec > 32 && nvec <= 64 && items.rows_sorted && sizeof(TIn) == 4 &&
         (sc.n_own < 0 || sizeof(TOut) == 4) && items.nsegs + items.nshort > 0) {
@@ -1130,7 +1130,7 @@ void spmm_typed(const int64_t* rp, const int32_t* col, const float* w, const flo
         const int64_t blocks = (n_items + (int64_t)wpb * 2 - 1) / ((int64_t)wpb * 2);
         SpmmArgs g;
         g.rp = rp; g.col = col; g.w = w; g.rowscale = rowscale;
-        g.a_rows = a_rows; g.n_a = n_a; g.b_rows = b_rows; g.out = out; g.d = d; g.ld = d;
+        g.a_rows = a_rows; g.n_a = n_a; g.b_rows = b_rows; g.out = out; g.d = d; g.ld = ld;
         g.it = items; g.partial = partial;
         g.map_n_own = sc.n_own; g.map_base = sc.base_row; g.map_idx = sc.idx; g.map_first = sc.first;
         g.bias = sc.bias; g.relu = sc.relu;
@@ -1146,7 +1146,7 @@ void spmm_typed(const int64_t* rp, const int32_t* col, const float* w, const flo
         const int64_t blocks = (n_items + (int64_t)wpb * S - 1) / ((int64_t)wpb * S);
         SpmmArgs g;
         g.rp = rp; g.col = col; g.w = w; g.rowscale = rowscale;
-        g.a_rows = a_rows; g.n_a = n_a; g.b_rows = b_rows; g.out = out; g.d = d; g.ld = d;
+        g.a_rows = a_rows; g.n_a = n_a; g.b_rows = b_rows; g.out = out; g.d = d; g.ld = ld;
         g.it = items; g.partial = partial;
         g.map_n_own = sc.n_own; g.map_base = sc.base_row; g.map_idx = sc.idx; g.map_first = sc.first;
         g.bias = sc.bias; g.relu = sc.relu;
@@ -1174,7 +1174,7 @@ void spmm_typed(const int64_t* rp, const int32_t* col, const float* w, const flo
         g.rp = rp; g.col = col; g.w = w; g.rowscale = rowscale;
         g.a_rows = static_cast<const TIn*>(a_rows) + c0; g.n_a = n_a;
         g.b_rows = b_rows ? static_cast<const TIn*>(b_rows) + c0 : nullptr;
-        g.out = static_cast<TOut*>(out) + c0; g.d = dc; g.ld = d; g.it = items;
+        g.out = static_cast<TOut*>(out) + c0; g.d = dc; g.ld = ld; g.it = items;
         g.partial = partial + c0;
         g.map_n_own = sc.n_own; g.map_base = sc.base_row; g.map_idx = sc.idx; g.map_first = sc.first;
         g.bias = sc.bias ? sc.bias + c0 : nullptr; g.relu = sc.relu;
@@ -1202,15 +1202,15 @@ void spmm_typed(const int64_t* rp, const int32_t* col, const float* w, const flo
 
 template <typename TOut>
 void spmm_reduce_typed(const float* rowscale, void* out, int32_t d, const SpmmItems& items,
-                       float* partial, const SpmmScatter& sc, hipStream_t s)
+                       float* partial, const SpmmScatter& sc, hipStream_t s, int32_t ld)
 {
     const int wpb = kBlock / kWave;
     SpmmArgs g{};
-    g.rowscale = rowscale; g.out = out; g.d = d; g.ld = d; g.it = items; g.partial = partial;
+    g.rowscale = rowscale; g.out = out; g.d = d; g.ld = ld; g.it = items; g.partial = partial;
     g.map_n_own = sc.n_own; g.map_base = sc.base_row; g.map_idx = sc.idx; g.map_first = sc.first;
     g.bias = sc.bias; g.relu = sc.relu;
     const dim3 rgrid((unsigned)((items.nlong + wpb - 1) / wpb), (unsigned)((d + 255) / 256));
-    if (d % 4 == 0) hipLaunchKernelGGL((k_spmm_long_reduce<TOut, true>), rgrid, dim3(kBlock), 0, s, g);
+    if (d % 4 == 0 && ld % 4 == 0) hipLaunchKernelGGL((k_spmm_long_reduce<TOut, true>), rgrid, dim3(kBlock), 0, s, g);
     else hipLaunchKernelGGL((k_spmm_long_reduce<TOut, false>), rgrid, dim3(kBlock), 0, s, g);
 }
 
@@ -1219,24 +1219,27 @@ void spmm_reduce_typed(const float* rowscale, void* out, int32_t d, const SpmmIt
 void launch_spmm(const int64_t* rp, const int32_t* col, const float* w, const float* rowscale,
                  const void* a_rows, int64_t n_a, const void* b_rows, void* out, int64_t nrows,
                  int32_t d, int in_bf16, int out_bf16, const SpmmItems& items, float* partial,
-                 int column_slices, const SpmmScatter& sc, hipStream_t s)
+                 int column_slices, const SpmmScatter& sc, hipStream_t s, int32_t ld)
 {
     if (nrows <= 0 || d <= 0 || items.nsegs + items.nranges <= 0) return;
-    const bool sl = column_slices != 0;
+    if (ld <= 0) ld = d;
+    // rows ld elements apart: the column-sliced kernel cuts whole rows, so only for ld = d
+    const bool sl = column_slices != 0 && ld == d;
     if (!in_bf16)
-        spmm_typed<float, float>(rp, col, w, rowscale, a_rows, n_a, b_rows, out, d, items, partial, sl, sc, s);
+        spmm_typed<float, float>(rp, col, w, rowscale, a_rows, n_a, b_rows, out, d, items, partial, sl, sc, s, ld);
     else if (out_bf16)
-        spmm_typed<uint16_t, uint16_t>(rp, col, w, rowscale, a_rows, n_a, b_rows, out, d, items, partial, sl, sc, s);
+        spmm_typed<uint16_t, uint16_t>(rp, col, w, rowscale, a_rows, n_a, b_rows, out, d, items, partial, sl, sc, s, ld);
     else
-        spmm_typed<uint16_t, float>(rp, col, w, rowscale, a_rows, n_a, b_rows, out, d, items, partial, sl, sc, s);
+        spmm_typed<uint16_t, float>(rp, col, w, rowscale, a_rows, n_a, b_rows, out, d, items, partial, sl, sc, s, ld);
 }
 
 void launch_spmm_reduce(const float* rowscale, void* out, int32_t d, int out_bf16,
-                        const SpmmItems& items, float* partial, const SpmmScatter& sc, hipStream_t s)
+                        const SpmmItems& items, float* partial, const SpmmScatter& sc, hipStream_t s, int32_t ld)
 {
     if (items.nlong <= 0 || d <= 0) return;
-    if (out_bf16) spmm_reduce_typed<uint16_t>(rowscale, out, d, items, partial, sc, s);
-    else spmm_reduce_typed<float>(rowscale, out, d, items, partial, sc, s);
+    if (ld <= 0) ld = d;
+    if (out_bf16) spmm_reduce_typed<uint16_t>(rowscale, out, d, items, partial, sc, s, ld);
+    else spmm_reduce_typed<float>(rowscale, out, d, items, partial, sc, s, ld);
 }
 
 bool spmm_gemm_fused_init();
