@@ -152,7 +152,19 @@ void gat_layer_fwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
     const float* bias = c->has_bias ? (const float*)c->w[(size_t)3 * (layer - 1) + 2] : nullptr;
     float* out = (float*)c->act[(size_t)layer - 1] + v0.r0 * v0.dout;
     const int relu = layer < c->L ? 1 : 0;
-    for (int32_t h = 0; h < nh; ++h) {
+    // heads side by side: every head in one launch, a column slice of the rows each (when the
+    // head width suits the slot kernels), else head by head
+    bool all_heads = false;
+    if (v0.side) {
+        Timed t(c, s, GNN_K_SPMM);
+        all_heads = launch_spmm_heads(rows.rp, rows.col, v0.att - v0.e0, v0.hs, nh, v0.f, v0.H + v0.own(), v0.np,
+                                      v0.stg, Z, v0.ldh, rows.items, segpart, SpmmScatter{}, s);
+    }
+    if (all_heads && rows.items.nlong > 0) {
+        Timed t(c, s, GNN_K_SPMM_REDUCE);
+        launch_spmm_reduce(nullptr, Z, v0.ldh, 0, rows.items, segpart, SpmmScatter{}, s);
+    }
+    for (int32_t h = 0; h < nh && !all_heads; ++h) {
         const GatView v = view(c, layer, p, h);
         // Z rows like the rows of H: the head's column block, or an array of its own
         float* Zh = Z + (v.side ? (int64_t)h * v.f : 0);
@@ -229,7 +241,13 @@ void gat_layer_bwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
         if (copy) return pad + (int64_t)h * v.np * v.fp;
         return dY + (v.side ? (int64_t)h * v.f : 0);
     };
-    for (int32_t h = 0; h < nh; ++h) {
+    const bool sliced = v0.side;      // every head in one launch, a column slice of the rows each
+    if (sliced) {
+        Timed t(c, s, GNN_K_SPMM);      // edge-wise products of every head: one source row read per entry and head
+        launch_gat_dots(rows.rp, rows.col, v0.e0, v0.np, v0.H + v0.own(), v0.stg, dY, v0.f, v0.ldh, v0.dal, rows.items,
+                        s, nh, v0.hs);
+    }
+    for (int32_t h = 0; h < nh && !sliced; ++h) {
         const GatView v = view(c, layer, p, h);
         if (copy) {
             Timed t(c, s, GNN_K_OTHER);
@@ -245,12 +263,22 @@ void gat_layer_bwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
         launch_gat_transposed(c->D.trp + t0, c->D.tperm, v0.e0, v0.np, v0.r0, bnd, titems, v0.pair, v0.twatt,
                               v0.gssrc, nh, v0.hs, s);
     }
-    for (int32_t h = 0; h < nh; ++h) {
+    SpmmScatter sc;
+    sc.n_own = v0.np;
+    sc.base_row = v0.r0;
+    sc.idx = bnd;
+    bool all_heads = false;
+    if (v0.side) {
+        Timed t(c, s, GNN_K_SPMM_T);
+        all_heads = launch_spmm_heads(c->D.trp + t0, c->D.tcol, v0.twatt - v0.e0, v0.hs, nh, v0.f, dY, v0.np, nullptr,
+                                      v0.gH, v0.ldh, titems, segpart, sc, s);
+    }
+    if (all_heads && titems.nlong > 0) {
+        Timed t(c, s, GNN_K_SPMM_REDUCE);
+        launch_spmm_reduce(nullptr, v0.gH, v0.ldh, 0, titems, segpart, sc, s);
+    }
+    for (int32_t h = 0; h < nh && !all_heads; ++h) {
         const GatView v = view(c, layer, p, h);
-        SpmmScatter sc;
-        sc.n_own = v.np;
-        sc.base_row = v.r0;
-        sc.idx = bnd;
         {
             Timed t(c, s, GNN_K_SPMM_T);
             launch_spmm(c->D.trp + t0, c->D.tcol, v.twatt - v.e0, nullptr, dy_of(v, h), v.np, nullptr, v.gH,

@@ -151,6 +151,14 @@ void launch_spmm(const int64_t* rp, const int32_t* col, const float* w, const fl
                  int32_t d, int in_bf16, int out_bf16, const SpmmItems& items, float* partial,
                  int column_slices /* allow the XCD column-sliced kernel */, const SpmmScatter& sc,
                  hipStream_t s, int32_t ld = 0);
+// The heads of a multi-head aggregation in one launch (fp32): rows of ld = nh f floats, column
+// block j of f floats weighted by the entry weights w + j wss; otherwise as launch_spmm (the long
+// rows' partial sums are combined by launch_spmm_reduce over all ld columns).  Returns false and
+// launches nothing when f is not 16, 32, 64 or 128 floats or the plan lists no short rows: the
+// caller then aggregates head by head.
+bool launch_spmm_heads(const int64_t* rp, const int32_t* col, const float* w, int64_t wss, int32_t nh, int32_t f,
+                       const float* a_rows, int64_t n_a, const float* b_rows, float* out, int32_t ld,
+                       const SpmmItems& items, float* partial, const SpmmScatter& sc, hipStream_t s);
 // Aggregation fused with the transform, fp32: y[r,:] = act(Z[r,:] W (+ xself[r,:] Ws) + bias) with
 // Z as launch_spmm would compute it, kept in LDS.  zlong: n_a x din floats of scratch for the
 // rows that are cut into segments.  Only when spmm_gemm_fused_ok() (d_in in 36..128, a multiple
@@ -297,10 +305,12 @@ void launch_gat_scores(const float* H, int32_t ld, int32_t f, int64_t rows, cons
 // att[e - e0] = softmax over each row of LeakyReLU_0.2(s_src(col e) + s_dst(row))
 // segwork: 3 floats per head and segment of the partition's long rows (scratch of the segment-parallel passes)
 void launch_gat_attention(const GatRowsHost& h, float* att, float* segwork, hipStream_t s);
-// dal[e - e0] = dy[row, :d] . src(col e)[:d]  (rows ld floats apart; d and ld multiples of 4)
+// dal[e - e0] = dy[row, :d] . src(col e)[:d]  (rows ld floats apart; d and ld multiples of 4).
+// nslice > 1: the same for nslice heads lying side by side, in one launch: head j on columns
+// [j d, (j + 1) d) of every row, its products in dal + j dal_stride.
 void launch_gat_dots(const int64_t* rp, const int32_t* col, int64_t e0, int64_t n_own, const float* a_rows,
                      const float* b_rows, const float* dy, int32_t d, int32_t ld, float* dal, const SpmmItems& items,
-                     hipStream_t s);
+                     hipStream_t s, int32_t nslice = 1, int64_t dal_stride = 0);
 // gradient of the pre-activation scores (through softmax and LeakyReLU) from att and dal, every
 // head: pair[((e - e0) nh + h) 2 + {0, 1}] = att, dpre (an entry's values of all heads side by
 // side, for the transposed pass); gs_dst_own[row nh + h] = row sum of dpre

@@ -602,6 +602,12 @@ struct GatDotArgs {
     int32_t ld;                 // row stride of H, staging and dy (multiple of 4)
     int32_t d;                  // columns of those rows the products run over (multiple of 4)
     float* dal;
+    // nslice > 1: one launch for the heads of a layer whose heads lie side by side: workgroup b
+    // takes head b % nslice, i.e. columns [head d, (head + 1) d) of every row and the head's array
+    // of products, dal_stride floats on (consecutive workgroups, on different XCDs, read different
+    // columns of the same source rows)
+    int32_t nslice;
+    int64_t dal_stride;
     SpmmItems it;
 };
 template <int G, int NV>
@@ -662,10 +668,19 @@ __device__ inline void dot_entries(const GatDotArgs& g, int32_t row, int64_t eb,
     }
 }
 template <int G, int NV>
-__global__ __launch_bounds__(kBlock) void k_gat_dots(const GatDotArgs g)
+__global__ __launch_bounds__(kBlock) void k_gat_dots(GatDotArgs g)
 {
     const int lane = threadIdx.x % kWave;
-    const int64_t item = (int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;
+    unsigned blk = blockIdx.x;
+    if (g.nslice > 1) {
+        const int64_t hd = blk % (unsigned)g.nslice;
+        blk /= (unsigned)g.nslice;
+        g.a_rows += hd * g.d;
+        g.b_rows += hd * g.d;
+        g.dy += hd * g.d;
+        g.dal += hd * g.dal_stride;
+    }
+    const int64_t item = (int64_t)blk * (kBlock / kWave) + threadIdx.x / kWave;
     if (item < g.it.nsegs) {
         const int64_t eb = g.it.seg_begin[item];
         dot_entries<G, NV>(g, g.it.seg_row[item], eb, eb + g.it.seg_len[item], lane);
@@ -861,14 +876,16 @@ void launch_gat_transposed(const int64_t* trp, const int32_t* tperm, int64_t e0,
 
 void launch_gat_dots(const int64_t* rp, const int32_t* col, int64_t e0, int64_t n_own, const float* a_rows,
                      const float* b_rows, const float* dy, int32_t d, int32_t ld, float* dal, const SpmmItems& items,
-                     hipStream_t s)
+                     hipStream_t s, int32_t nslice, int64_t dal_stride)
 {
     const int64_t nitems = items.nsegs + items.nranges;
     if (nitems <= 0) return;
+    if (nslice < 1) nslice = 1;
     GatDotArgs g;
     g.rp = rp; g.col = col; g.e0 = e0; g.n_own = n_own; g.a_rows = a_rows; g.b_rows = b_rows; g.dy = dy;
     g.ld = ld; g.d = d; g.dal = dal; g.it = items;
-    const dim3 grid((unsigned)((nitems + 3) / 4)), block(kBlock);
+    g.nslice = nslice; g.dal_stride = dal_stride;
+    const dim3 grid((unsigned)((nitems + 3) / 4 * nslice)), block(kBlock);
     const int vecs = d / 4;
     if (vecs <= 4) hipLaunchKernelGGL((k_gat_dots<4, 1>), grid, block, 0, s, g);
     else if (vecs <= 8) hipLaunchKernelGGL((k_gat_dots<8, 1>), grid, block, 0, s, g);

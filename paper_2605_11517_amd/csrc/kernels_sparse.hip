@@ -104,6 +104,7 @@ struct SpmmArgs {
     const int64_t* rp;
     const int32_t* col;
     const float* w;
+    int64_t wss = 0;        // column-sliced launches: the entry weights of slice s start at w + s wss
     const float* rowscale;
     const void* a_rows;     // element type TIn
     int64_t n_a;
@@ -385,6 +386,7 @@ __global__ __launch_bounds__(kBlock) void k_spmm_slots(const SpmmArgs g, int32_t
     const int coff_raw = (int)(blk % (unsigned)nslices) * (G * EPV) + gl * EPV;
     const bool live = coff_raw < g.d;
     const int coff = live ? coff_raw : 0;
+    const float* wsl = g.w ? g.w + (int64_t)(blk % (unsigned)nslices) * g.wss : nullptr;   // this slice's weights
     blk /= (unsigned)nslices;
     const int64_t item = ((int64_t)blk * (kBlock / kWave) + threadIdx.x / kWave) * S + slot;
 
@@ -425,7 +427,7 @@ __global__ __launch_bounds__(kBlock) void k_spmm_slots(const SpmmArgs g, int32_t
         float my_w = 0.f;
         if (e0 + gl < len) {
             my_c = g.col[e_begin + e0 + gl];
-            my_w = g.w ? g.w[e_begin + e0 + gl] : 1.f;
+            my_w = wsl ? wsl[e_begin + e0 + gl] : 1.f;
         }
         const int cnt = len - e0;                     // entries this slot still has (may be <= 0)
         const int lead_cnt = maxlen - e0 < G ? maxlen - e0 : G;
@@ -522,6 +524,7 @@ __global__ __launch_bounds__(kBlock) void k_spmm_short(const SpmmArgs g, int32_t
         live[v] = raw < g.d;
         coff[v] = live[v] ? raw : 0;
     }
+    const float* wsl = g.w ? g.w + (int64_t)(blk % (unsigned)nslices) * g.wss : nullptr;   // this slice's weights
     blk /= (unsigned)nslices;
     const int64_t item = ((int64_t)blk * (kBlock / kWave) + threadIdx.x / kWave) * S + slot;
 
@@ -564,7 +567,7 @@ __global__ __launch_bounds__(kBlock) void k_spmm_short(const SpmmArgs g, int32_t
         float my_w = 0.f;
         if (e0 + gl < len) {
             my_c = g.col[e_begin + e0 + gl];
-            my_w = g.w ? g.w[e_begin + e0 + gl] : 1.f;
+            my_w = wsl ? wsl[e_begin + e0 + gl] : 1.f;
         }
         const int cnt = len - e0;                     // entries this slot still has (may be <= 0)
         const int lead_cnt = maxlen - e0 < G ? maxlen - e0 : G;
@@ -1240,6 +1243,41 @@ void launch_spmm_reduce(const float* rowscale, void* out, int32_t d, int out_bf1
     if (ld <= 0) ld = d;
     if (out_bf16) spmm_reduce_typed<uint16_t>(rowscale, out, d, items, partial, sc, s, ld);
     else spmm_reduce_typed<float>(rowscale, out, d, items, partial, sc, s, ld);
+}
+
+// One launch for the heads of a multi-head aggregation whose heads lie side by side in rows of
+// `ld` floats: nh column slices of f floats, slice j weighted by w + j wss (fp32).  The slices of
+// a work item go to consecutive workgroups and so to different XCDs, whose caches then hold
+// different columns of the source rows.  False (nothing launched) when the slice width is not
+// 4, 8, 16 or 32 vectors of 16 bytes or the plan has no list of short rows.
+bool launch_spmm_heads(const int64_t* rp, const int32_t* col, const float* w, int64_t wss, int32_t nh, int32_t f,
+                       const float* a_rows, int64_t n_a, const float* b_rows, float* out, int32_t ld,
+                       const SpmmItems& items, float* partial, const SpmmScatter& sc, hipStream_t s)
+{
+    const int G = f / 4;
+    if (f % 4 != 0 || !(G == 4 || G == 8 || G == 16 || G == 32) || nh * f != ld || !items.rows_sorted) return false;
+    const int64_t n_items = items.nsegs + items.nshort;
+    if (n_items <= 0) return true;
+    const int wpb = kBlock / kWave, S = kWave / G;
+    const int64_t blocks = (n_items + (int64_t)wpb * S - 1) / ((int64_t)wpb * S);
+    if (blocks * nh >= ((int64_t)1 << 31)) return false;
+    SpmmArgs g;
+    g.rp = rp; g.col = col; g.w = w; g.wss = wss; g.rowscale = nullptr;
+    g.a_rows = a_rows; g.n_a = n_a; g.b_rows = b_rows; g.out = out; g.d = ld; g.ld = ld;
+    g.it = items; g.partial = partial;
+    g.map_n_own = sc.n_own; g.map_base = sc.base_row; g.map_idx = sc.idx; g.map_first = sc.first;
+    g.bias = sc.bias; g.relu = sc.relu;
+    const dim3 grid((unsigned)(blocks * nh));
+    // operators of short rows: the variant with four loads in flight per slot (64-bit addresses)
+    const bool few2 = items.avg_len > 0.f && items.avg_len < short_rows_max();
+    if (G == 4) hipLaunchKernelGGL((k_spmm_slots<float, float, 4>), grid, dim3(kBlock), 0, s, g, nh);
+    else if (G == 8 && few2) hipLaunchKernelGGL((k_spmm_short<float, float, 8, 4, 1, false>), grid, dim3(kBlock), 0, s, g, nh);
+    else if (G == 8) hipLaunchKernelGGL((k_spmm_slots<float, float, 8>), grid, dim3(kBlock), 0, s, g, nh);
+    else if (G == 16 && few2) hipLaunchKernelGGL((k_spmm_short<float, float, 16, 4, 1, false>), grid, dim3(kBlock), 0, s, g, nh);
+    else if (G == 16) hipLaunchKernelGGL((k_spmm_slots<float, float, 16>), grid, dim3(kBlock), 0, s, g, nh);
+    else if (few2) hipLaunchKernelGGL((k_spmm_short<float, float, 32, 4, 1, false>), grid, dim3(kBlock), 0, s, g, nh);
+    else hipLaunchKernelGGL((k_spmm_slots<float, float, 32>), grid, dim3(kBlock), 0, s, g, nh);
+    return true;
 }
 
 bool spmm_gemm_fused_init();

@@ -1258,6 +1258,8 @@ def test_graph_attention_epoch_matches_oracle(name, dims, k, mode):
     ("mini_gcn_directed", (20, 15, 12, 6), (3, 4, 2), 7, "random"),      # 5- and 3-column heads: padded, unaligned slices of W
     ("tiny", (64, 64, 16), (8, 2), 4, "switching"),                      # hub rows cut into segments, per head
     ("mini_sage", (24, 256, 7), (4, 1), 1, "random"),                    # 64-column heads, k = 1
+    ("tiny", (64, 64, 32), (4, 2), 4, "switching"),                      # 16-column heads in one aggregation launch, hub rows, boundary rows
+    ("mini_sage", (24, 128, 64, 7), (4, 2, 1), 5, "lp"),                 # 32-column heads in one launch
 ])
 def test_multi_head_attention_epoch_matches_oracle(name, dims, heads, k, mode):
     """Several attention heads per layer (gnn_set_gat_heads): every array of the epoch against the
