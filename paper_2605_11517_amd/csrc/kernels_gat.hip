@@ -110,6 +110,41 @@ constexpr int kPerLane = kSpmmSegment / kWave;
 // the scores of the HB heads of a neighbour lie side by side and are fetched together (VEC: as
 // one 16-byte vector; needs HB = 4 and nh a multiple of 4), and the HB reductions run beside
 // each other instead of one after the other.
+// The same for heads lying side by side in rows of nh f floats, f a power of two between 4 and
+// 256: one wavefront per row reads the whole row (a 16-byte vector per lane and 256-column block)
+// and the f / 4 lanes of a head add up their products.
+__global__ __launch_bounds__(kBlock) void k_gat_scores_side(const float* __restrict__ H, int32_t ld, int32_t f,
+                                                            int64_t rows, const float* __restrict__ a_src,
+                                                            const float* __restrict__ a_dst,
+                                                            float* __restrict__ ssrc, float* __restrict__ sdst,
+                                                            int32_t nh)
+{
+    const int lane = threadIdx.x % kWave;
+    const int64_t r = (int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;
+    if (r >= rows) return;
+    const int32_t d = nh * f;
+    const int gl = f / 4;                       // lanes per head
+    for (int32_t c0 = 0; c0 < d; c0 += 4 * kWave) {
+        const int32_t c = c0 + 4 * lane;
+        float s1 = 0.f, s2 = 0.f;
+        if (c < d) {
+            const float4 h = *reinterpret_cast<const float4*>(H + r * ld + c);
+            const float4 as = *reinterpret_cast<const float4*>(a_src + c);
+            const float4 ad = *reinterpret_cast<const float4*>(a_dst + c);
+            s1 = (h.x * as.x + h.y * as.y) + (h.z * as.z + h.w * as.w);
+            s2 = (h.x * ad.x + h.y * ad.y) + (h.z * ad.z + h.w * ad.w);
+        }
+        for (int m = 1; m < gl; m <<= 1) {
+            s1 += __shfl_xor(s1, m, kWave);
+            s2 += __shfl_xor(s2, m, kWave);
+        }
+        if (c < d && lane % gl == 0) {
+            ssrc[r * nh + c / f] = s1;
+            sdst[r * nh + c / f] = s2;
+        }
+    }
+}
+
 template <int HB, bool VEC>
 __device__ inline void load_scores(const GatRows& g, int32_t c, int32_t h0, int nhb, float (&out)[HB])
 {
@@ -773,6 +808,13 @@ void launch_gat_scores(const float* H, int32_t ld, int32_t f, int64_t rows, cons
 {
     if (rows <= 0) return;
     const int64_t blocks = (rows + kBlock / kWave - 1) / (kBlock / kWave);
+    const bool aligned = ((reinterpret_cast<uintptr_t>(H) | reinterpret_cast<uintptr_t>(a_src) |
+                           reinterpret_cast<uintptr_t>(a_dst)) & 15) == 0 && ld % 4 == 0;
+    if (nh > 1 && head_off == f && f >= 4 && f <= 256 && (f & (f - 1)) == 0 && aligned) {
+        hipLaunchKernelGGL(k_gat_scores_side, dim3((unsigned)blocks), dim3(kBlock), 0, s, H, ld, f, rows, a_src, a_dst,
+                           ssrc, sdst, nh);
+        return;
+    }
     hipLaunchKernelGGL(k_gat_scores, dim3((unsigned)blocks, (unsigned)nh), dim3(kBlock), 0, s, H, ld, f, rows, a_src,
                        a_dst, ssrc, sdst, nh, head_off);
 }

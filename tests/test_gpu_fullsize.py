@@ -417,7 +417,8 @@ def test_mid_gat_workload_sampled(capsys, heads):
     say("GPU epoch done, loss %.6f" % loss)
     deg = np.diff(rowptr)
     rng = np.random.default_rng(5)
-    V = np.unique(np.concatenate([rng.choice(n, 504, replace=False), np.argsort(deg)[-8:]]))
+    # (with heads the per-vertex recomputation runs head by head: fewer sampled vertices)
+    V = np.unique(np.concatenate([rng.choice(n, 504 if heads is None else 120, replace=False), np.argsort(deg)[-8:]]))
     lref, gref = og.loss(got["act"][L - 1], y, m)
     assert abs(loss - lref) <= TOL * abs(lref)
     worst = {"gact[%d]" % (L - 1): rel_err(got["gact"][L - 1], gref)}
