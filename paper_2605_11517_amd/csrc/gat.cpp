@@ -261,7 +261,7 @@ void gat_layer_bwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
         Timed t(c, s, GNN_K_OTHER);     // every head
         launch_gat_bwd_scalars(rows, v0.att, v0.dal, v0.pair, v0.gsdst + v0.r0 * nh, segpart, s);
         launch_gat_transposed(c->D.trp + t0, c->D.tperm, v0.e0, v0.np, v0.r0, bnd, titems, v0.pair, v0.twatt,
-                              v0.gssrc, nh, v0.hs, s);
+                              v0.gssrc, nh, v0.hs, segpart, s);
     }
     SpmmScatter sc;
     sc.n_own = v0.np;

@@ -317,10 +317,11 @@ void launch_gat_dots(const int64_t* rp, const int32_t* col, int64_t e0, int64_t 
 void launch_gat_bwd_scalars(const GatRowsHost& h, const float* att, const float* dal, float* pair,
                             float* gs_dst_own, float* segwork, hipStream_t s);
 // transposed rows, every head: tw_att[h hs + pos - e0] = att of entry tperm[pos];
-// gs_src[(owner row of transposed row i) nh + h] += sum over the row of dpre of entry tperm[pos]
+// gs_src[(owner row of transposed row i) nh + h] += sum over the row of dpre of entry tperm[pos];
+// segwork: nh floats per segment of the partition's long transposed rows
 void launch_gat_transposed(const int64_t* trp, const int32_t* tperm, int64_t e0, int64_t n_own,
                            int64_t base_row, const int32_t* bnd, const SpmmItems& items, const float* pair,
-                           float* tw_att, float* gs_src, int32_t nh, int64_t hs, hipStream_t s);
+                           float* tw_att, float* gs_src, int32_t nh, int64_t hs, float* segwork, hipStream_t s);
 // gH[r, j] += gs_src[r nh + j / fh] a_src[j] + gs_dst[r nh + j / fh] a_dst[j] over `rows` rows and f
 // columns (column j belongs to head j / fh of the score arrays; fh = f and offset pointers: one
 // head); partial column sums of gs_src H and gs_dst H (2 f floats per block of 256 rows) for the

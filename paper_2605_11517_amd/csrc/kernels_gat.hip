@@ -518,52 +518,62 @@ struct GatTRows {
     const int32_t* long_row;
     int64_t nlong;
 };
-// one head of one long transposed row, a workgroup per row
-__device__ inline void trow_block(const GatTRows& g, int32_t i, int32_t h, const float* __restrict__ pair,
-                                  float* __restrict__ tw_att, float* __restrict__ gs_src, float* sm)
+// Long transposed rows (a hub as a source: up to 10^5 destinations in one partition) are cut
+// into the aggregation's segments like the long forward rows: one wavefront per segment and all
+// heads, then one wavefront per row adds the segments' sums in segment order.  (A workgroup per
+// row walked a hub's entries in a hundred dependent steps: 245 us per launch, whatever the heads.)
+__global__ __launch_bounds__(kBlock) void k_gat_tsegs(const GatTRows g, const GatSegs q,
+                                                      const float* __restrict__ pair, float* __restrict__ tw_att,
+                                                      float* __restrict__ stat)
 {
-    constexpr int T = kBlock;
-    const int t = threadIdx.x;
-    const int64_t eb = g.trp[i], ee = g.trp[i + 1];
-    float s = 0.f;
-    constexpr int U = 4;
-    for (int64_t e = eb + t; e < ee; e += (int64_t)T * U) {
-        int32_t fe[U];
-        float2 v[U];
+    const int t = threadIdx.x % kWave;
+    const int64_t sgi = (int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;
+    if (sgi >= q.nsegs) return;
+    const int64_t eb = q.seg_begin[sgi], ee = eb + q.seg_len[sgi];
+    int32_t fe[kPerLane];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int64_t eu = e + (int64_t)u * T;
-            fe[u] = g.tperm[eu < ee ? eu : ee - 1];
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-            v[u] = *reinterpret_cast<const float2*>(pair + ((int64_t)fe[u] * g.nh + h) * 2);
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int64_t eu = e + (int64_t)u * T;
-            if (eu < ee) {
-                tw_att[h * g.hs + eu - g.e0] = v[u].x;
-                s += v[u].y;
-            }
-        }
+    for (int i = 0; i < kPerLane; ++i) {
+        const int64_t e = eb + t + (int64_t)i * kWave;
+        fe[i] = e < ee ? g.tperm[e] : -1;
     }
-    s = red_sum<true>(s, sm);
-    if (t == 0) {
-        const int64_t r = i < g.n_own ? g.base_row + i : (int64_t)g.bnd[i - g.n_own];
-        gs_src[r * g.nh + h] += s;
+    for (int32_t h = 0; h < g.nh; ++h) {
+        float2 v[kPerLane];
+#pragma unroll
+        for (int i = 0; i < kPerLane; ++i)
+            v[i] = fe[i] >= 0 ? *reinterpret_cast<const float2*>(pair + ((int64_t)fe[i] * g.nh + h) * 2)
+                              : make_float2(0.f, 0.f);
+        float sum = 0.f;
+#pragma unroll
+        for (int i = 0; i < kPerLane; ++i) {
+            const int64_t e = eb + t + (int64_t)i * kWave;
+            if (e < ee) tw_att[h * g.hs + e - g.e0] = v[i].x;
+            sum += v[i].y;
+        }
+        sum = wave_sum(sum);
+        if (t == 0) stat[(int64_t)h * q.nsegs + sgi] = sum;
+    }
+}
+__global__ __launch_bounds__(kBlock) void k_gat_tcombine(const GatTRows g, const GatSegs q,
+                                                         const float* __restrict__ stat, float* __restrict__ gs_src)
+{
+    const int t = threadIdx.x % kWave;
+    const int64_t i = (int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;
+    if (i >= q.nlong) return;
+    const int32_t first = q.long_first[i], ns = q.long_nseg[i], row = q.long_row[i];
+    const int64_t r = row < g.n_own ? g.base_row + row : (int64_t)g.bnd[row - g.n_own];
+    for (int32_t h = 0; h < g.nh; ++h) {
+        float v = 0.f;
+        for (int32_t j = t; j < ns; j += kWave) v += stat[(int64_t)h * q.nsegs + first + j];
+        v = wave_sum(v);
+        if (t == 0) gs_src[r * g.nh + h] += v;
     }
 }
 // EVEN: nh is even, two heads' pairs are read as one 16-byte vector
-template <bool BLOCK, bool EVEN>
+template <bool EVEN>
 __global__ __launch_bounds__(kBlock) void k_gat_trows(const GatTRows g, const float* __restrict__ pair,
                                                       float* __restrict__ tw_att, float* __restrict__ gs_src)
 {
-    __shared__ float sm[kBlock / kWave];
-    if (BLOCK) {
-        const int64_t i = blockIdx.x;
-        if (i >= g.nlong) return;
-        for (int32_t h = 0; h < g.nh; ++h) trow_block(g, g.long_row[i], h, pair, tw_att, gs_src, sm);
-    } else {
+    {
         // transposed rows are short (a source feeds about ten destinations of a partition): a
         // group of 16 lanes takes a row, four rows of the item at a time, four heads at a time
         constexpr int GW = 16, HB = 4;
@@ -899,7 +909,7 @@ void launch_gat_bwd_scalars(const GatRowsHost& h, const float* att, const float*
 
 void launch_gat_transposed(const int64_t* trp, const int32_t* tperm, int64_t e0, int64_t n_own,
                            int64_t base_row, const int32_t* bnd, const SpmmItems& items, const float* pair,
-                           float* tw_att, float* gs_src, int32_t nh, int64_t hs, hipStream_t s)
+                           float* tw_att, float* gs_src, int32_t nh, int64_t hs, float* segwork, hipStream_t s)
 {
     GatTRows g;
     g.trp = trp; g.tperm = tperm; g.e0 = e0; g.n_own = n_own; g.base_row = base_row; g.bnd = bnd;
@@ -908,12 +918,19 @@ void launch_gat_transposed(const int64_t* trp, const int32_t* tperm, int64_t e0,
     g.long_row = items.long_row; g.nlong = items.nlong;
     if (g.nranges > 0) {
         const dim3 grid((unsigned)((g.nranges + 3) / 4)), b(kBlock);
-        if (nh % 2 == 0) hipLaunchKernelGGL((k_gat_trows<false, true>), grid, b, 0, s, g, pair, tw_att, gs_src);
-        else hipLaunchKernelGGL((k_gat_trows<false, false>), grid, b, 0, s, g, pair, tw_att, gs_src);
+        if (nh % 2 == 0) hipLaunchKernelGGL((k_gat_trows<true>), grid, b, 0, s, g, pair, tw_att, gs_src);
+        else hipLaunchKernelGGL((k_gat_trows<false>), grid, b, 0, s, g, pair, tw_att, gs_src);
     }
-    if (g.nlong > 0)
-        hipLaunchKernelGGL((k_gat_trows<true, false>), dim3((unsigned)g.nlong), dim3(kBlock), 0, s, g, pair, tw_att,
-                           gs_src);
+    if (items.nlong > 0 && items.nsegs > 0) {
+        GatSegs q;
+        q.seg_row = items.seg_row; q.seg_begin = items.seg_begin; q.seg_len = items.seg_len; q.nsegs = items.nsegs;
+        q.long_row = items.long_row; q.long_first = items.long_first; q.long_nseg = items.long_nseg;
+        q.nlong = items.nlong;
+        hipLaunchKernelGGL(k_gat_tsegs, dim3((unsigned)((q.nsegs + 3) / 4)), dim3(kBlock), 0, s, g, q, pair, tw_att,
+                           segwork);
+        hipLaunchKernelGGL(k_gat_tcombine, dim3((unsigned)((q.nlong + 3) / 4)), dim3(kBlock), 0, s, g, q,
+                           (const float*)segwork, gs_src);
+    }
 }
 
 void launch_gat_dots(const int64_t* rp, const int32_t* col, int64_t e0, int64_t n_own, const float* a_rows,
