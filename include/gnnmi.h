@@ -236,7 +236,7 @@ gnn_status gnn_to_bf16(gnn_ctx *ctx, const float *src, void *dst, int64_t count,
  * 0..k-1, GNN_ESTATE when unbound. */
 gnn_status gnn_gather_boundary(gnn_ctx *ctx, int32_t layer, int32_t p, void *stream);
 
-/* Gather fused into the aggregation (resident schedule, GNN_GCN and GNN_SAGE_MEAN).  The gather
+/* Gather fused into the aggregation (resident schedule).  The gather
  * step exists because A^{l-1} lives outside device memory and only the rows a partition needs
  * are brought in; when A^{l-1} is resident the staging copy is one read and one write of every
  * boundary row on top of the aggregation's own reads of it.  With on = 1 the aggregation
@@ -246,8 +246,10 @@ gnn_status gnn_gather_boundary(gnn_ctx *ctx, int32_t layer, int32_t p, void *str
  * the next gnn_bind and kept until gnn_destroy).  gnn_gather_boundary then launches nothing and
  * only records which (layer, partition) the following gnn_layer_fwd / gnn_layer_bwd may work
  * on; staging is not written.  Every sum takes its terms in the same order, so all results are
- * the bits of the staged path.  Default 0 (the paper's step, through staging).  The setting has
- * no effect with a streaming budget or GNN_GAT layers (gnn_gather_is_fused reports 0 there).
+ * the bits of the staged path.  GNN_GAT: the attention passes, the aggregation and the edge-wise
+ * products read the rows of H and the scores of boundary vertices the same way.  Default 0 (the
+ * paper's step, through staging).  The setting has no effect with a streaming budget
+ * (gnn_gather_is_fused reports 0 there).
  * GNN_EINVAL for on outside {0, 1}, GNN_ENOMEM / GNN_EHIP if the index array cannot be set up. */
 gnn_status gnn_set_gather_fusion(gnn_ctx *ctx, int32_t on);
 /* Backward pass of the output layer over train vertices only (resident schedule, GNN_GCN and

@@ -36,6 +36,14 @@ struct GatView {
     int64_t r0, np, nb, e0, n, hs;
     int32_t din, dout, nh, f, fp, ldh;
     bool side;                  // heads side by side
+    // Gather fused into the kernels (gnn_set_gather_fusion): rows of H and scores of boundary
+    // vertices are read where they lie, through column indices that name rows of the whole-graph
+    // arrays, and nothing is staged.  `col`, `src` / `n_src` / `bsrc` describe the sources either
+    // way: columns below n_src are rows of src, the others rows of bsrc.
+    bool fused;
+    const int32_t* col;
+    const float *src, *bsrc;
+    int64_t n_src;
     float *H, *gH, *ssrc, *sdst, *gssrc, *gsdst, *bs, *att, *dal, *twatt, *pair, *stg;
     const float *W, *a_src, *a_dst;
     int64_t own() const { return r0 * ldh; }     // offset of the partition's first row in H / grad H
@@ -76,6 +84,11 @@ GatView view(gnn_ctx* c, int32_t layer, int32_t p, int32_t h)
     v.W = (const float*)c->w[(size_t)3 * (layer - 1)] + (int64_t)h * v.f;
     v.a_src = (const float*)c->w[(size_t)3 * (layer - 1) + 1] + (int64_t)h * v.f;
     v.a_dst = v.a_src + v.dout;
+    v.fused = c->gather_fused();
+    v.col = v.fused ? c->D.gcol : c->D.lcol;
+    v.src = v.fused ? v.H : v.H + v.own();
+    v.bsrc = v.fused ? nullptr : v.stg;
+    v.n_src = v.fused ? v.n : v.np;
     return v;
 }
 
@@ -83,10 +96,10 @@ GatRowsHost rows_of(gnn_ctx* c, const GatView& v, int32_t p)
 {
     GatRowsHost h;
     h.rp = c->D.rp + v.r0;
-    h.col = c->D.lcol;
+    h.col = v.col;
     h.e0 = v.e0;
-    h.n_own = v.np;
-    h.ssrc_own = v.ssrc + v.r0 * v.nh;
+    h.n_own = v.n_src;
+    h.ssrc_own = v.fused ? v.ssrc : v.ssrc + v.r0 * v.nh;
     h.ssrc_bnd = v.bs;
     h.sdst_own = v.sdst + v.r0 * v.nh;
     h.nh = v.nh;
@@ -128,6 +141,7 @@ void gat_gather(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
     const int32_t nh = c->nheads(layer);
     const int32_t* bnd = c->D.bnd + c->M.boff[(size_t)p];
     const GatView v0 = view(c, layer, p, 0);
+    if (v0.fused) return;            // the kernels read the boundary rows and scores themselves
     Timed t(c, s, GNN_K_GATHER);
     const int32_t steps = v0.side ? 1 : nh;
     for (int32_t h = 0; h < steps; ++h) {
@@ -157,8 +171,8 @@ void gat_layer_fwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
     bool all_heads = false;
     if (v0.side) {
         Timed t(c, s, GNN_K_SPMM);
-        all_heads = launch_spmm_heads(rows.rp, rows.col, v0.att - v0.e0, v0.hs, nh, v0.f, v0.H + v0.own(), v0.np,
-                                      v0.stg, Z, v0.ldh, rows.items, segpart, SpmmScatter{}, s);
+        all_heads = launch_spmm_heads(rows.rp, rows.col, v0.att - v0.e0, v0.hs, nh, v0.f, v0.src, v0.n_src,
+                                      v0.bsrc, Z, v0.ldh, rows.items, segpart, SpmmScatter{}, s);
     }
     if (all_heads && rows.items.nlong > 0) {
         Timed t(c, s, GNN_K_SPMM_REDUCE);
@@ -170,7 +184,7 @@ void gat_layer_fwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
         float* Zh = Z + (v.side ? (int64_t)h * v.f : 0);
         {
             Timed t(c, s, GNN_K_SPMM);
-            launch_spmm(rows.rp, rows.col, v.att - v.e0, nullptr, v.H + v.own(), v.np, v.stg, Zh, v.np, v.fp,
+            launch_spmm(rows.rp, rows.col, v.att - v.e0, nullptr, v.src, v.n_src, v.bsrc, Zh, v.np, v.fp,
                         0, 0, rows.items, segpart, 1, SpmmScatter{}, s, v.ldh);
         }
         if (rows.items.nlong > 0) {
@@ -244,7 +258,7 @@ void gat_layer_bwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
     const bool sliced = v0.side;      // every head in one launch, a column slice of the rows each
     if (sliced) {
         Timed t(c, s, GNN_K_SPMM);      // edge-wise products of every head: one source row read per entry and head
-        launch_gat_dots(rows.rp, rows.col, v0.e0, v0.np, v0.H + v0.own(), v0.stg, dY, v0.f, v0.ldh, v0.dal, rows.items,
+        launch_gat_dots(rows.rp, rows.col, v0.e0, v0.n_src, v0.src, v0.bsrc, dY, v0.f, v0.ldh, v0.dal, rows.items,
                         s, nh, v0.hs);
     }
     for (int32_t h = 0; h < nh && !sliced; ++h) {
@@ -254,7 +268,7 @@ void gat_layer_bwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
             launch_pad_rows(pad + (int64_t)h * v.np * v.fp, dY + (int64_t)h * v.f, v.np, v.f, v.fp, s, v.dout);
         }
         Timed t(c, s, GNN_K_SPMM);      // edge-wise products: one source row read per entry
-        launch_gat_dots(rows.rp, rows.col, v.e0, v.np, v.H + v.own(), v.stg, dy_of(v, h), v.fp, v.ldh, v.dal,
+        launch_gat_dots(rows.rp, rows.col, v.e0, v.n_src, v.src, v.bsrc, dy_of(v, h), v.fp, v.ldh, v.dal,
                         rows.items, s);
     }
     {

@@ -1206,7 +1206,7 @@ gnn_status gnn_bind(gnn_ctx* c, const void* feat, void* const* act, void* const*
                                    "scratch must be 16-byte aligned");
     gnn_status st = ensure_device(c);
     if (st != GNN_OK) return st;
-    if (c->fuse_gather && !c->streaming() && c->model != GNN_GAT && (st = ensure_global_columns(c)) != GNN_OK) return st;
+    if (c->fuse_gather && !c->streaming() && (st = ensure_global_columns(c)) != GNN_OK) return st;
     c->feat = tiered ? nullptr : (const char*)feat;
     c->act.assign((size_t)L, nullptr);
     c->gact.assign((size_t)L, nullptr);
@@ -1315,7 +1315,7 @@ gnn_status gnn_set_gather_fusion(gnn_ctx* c, int32_t on)
     if (on != 0 && on != 1) return c->fail(GNN_EINVAL, "gnn_set_gather_fusion takes 0 or 1");
     c->fuse_gather = on == 1;
     c->staged_layer = c->staged_p = -1;       // staging holds nothing the other mode could use
-    if (c->fuse_gather && c->D.ready && !c->streaming() && c->model != GNN_GAT) return ensure_global_columns(c);
+    if (c->fuse_gather && c->D.ready && !c->streaming()) return ensure_global_columns(c);
     return GNN_OK;
 }
 
@@ -1348,7 +1348,7 @@ gnn_status gnn_gather_is_fused(const gnn_ctx* c, int32_t* out)
 {
     if (!c || !out) return GNN_EINVAL;
     // the index array is set up by gnn_bind at the latest
-    *out = c->fuse_gather && !c->streaming() && c->model != GNN_GAT ? 1 : 0;
+    *out = c->fuse_gather && !c->streaming() ? 1 : 0;
     return GNN_OK;
 }
 

@@ -138,7 +138,7 @@ struct gnn_ctx {
     // Resident schedule: the aggregation reads the boundary rows A^{l-1}[B_p[i]] itself, through
     // column indices that name rows of the whole-graph array, and no staging copy is made
     bool fuse_gather = false;
-    bool gather_fused() const { return fuse_gather && !streaming() && model != GNN_GAT && D.gcol != nullptr; }
+    bool gather_fused() const { return fuse_gather && !streaming() && D.gcol != nullptr; }
     // The output layer's transposed aggregation runs over the operator entries of train vertices
     // only (the gradient of the loss is zero elsewhere); the sub-operator is built by gnn_bind
     bool masked_bwd = false;

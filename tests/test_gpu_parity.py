@@ -1251,6 +1251,16 @@ def test_graph_attention_epoch_matches_oracle(name, dims, k, mode):
     for key in ("act", "gact", "gW", "gWs", "gb"):
         for a, b in zip(r1[key], r2[key]):
             assert np.array_equal(a, b), key
+    # gather fused into the kernels: the same bits, staging untouched
+    s.set_gather_fusion(True)
+    assert s.ctx.gather_is_fused()
+    s.staging.fill_(0xFF)
+    assert s.epoch() == loss
+    r3 = s.results()
+    for key in ("act", "gact", "gW", "gWs", "gb"):
+        for a, b in zip(r1[key], r3[key]):
+            assert np.array_equal(a, b), ("fused gather", key)
+    assert bool((s.staging == 0xFF).all()), "staging was written although the gather is fused"
 
 
 @pytest.mark.parametrize("name,dims,heads,k,mode", [
@@ -1297,6 +1307,18 @@ def test_multi_head_attention_epoch_matches_oracle(name, dims, heads, k, mode):
     for key in ("act", "gact", "gW", "gWs", "gb"):
         for a, b in zip(got[key], r2[key]):
             assert np.array_equal(a, b), key
+    # gather fused into the kernels: rows of H and scores of boundary vertices read where they
+    # lie, nothing staged, the same bits
+    s.set_gather_fusion(True)
+    assert s.ctx.gather_is_fused()
+    s.staging.fill_(0xFF)
+    assert s.epoch() == loss
+    r3 = s.results()
+    for key in ("act", "gact", "gW", "gWs", "gb"):
+        for a, b in zip(got[key], r3[key]):
+            assert np.array_equal(a, b), ("fused gather", key)
+    assert bool((s.staging == 0xFF).all()), "staging was written although the gather is fused"
+    del s
     # the heads matter: the one-head model of the same weights gives another loss
     for wl in w:
         wl["heads"] = 1
