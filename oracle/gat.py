@@ -94,7 +94,7 @@ def layer_backward(dst, src, n, A, W, a_src, a_dst, cache, dY):
     return dict(gW=A.T @ dH, ga_src=da_src, ga_dst=da_dst, gb=dY.sum(axis=0), gA=dH @ W.T)
 
 
-def forward(rowptr, colidx, dims, X, weights):
+def forward(rowptr, colidx, dims, X, weights, drop=None):
     """``weights``: per layer a dict with ``W`` [d_in, d_out], ``a_src``, ``a_dst`` [d_out],
     ``b`` [d_out] or None, and optionally ``heads`` (default 1; must divide d_out).  Returns the activations A^1..A^L and the per-layer caches."""
     n = len(rowptr) - 1
@@ -111,25 +111,34 @@ def forward(rowptr, colidx, dims, X, weights):
                                  None if w.get("b") is None else np.asarray(w["b"], dtype=np.float64),
                                  relu=l < L - 1, heads=int(w.get("heads", 1)))
         cache["A_in"] = A_in
+        cache["on"] = A > 0                              # ReLU decision, before any dropout
+        if drop is not None and l < L - 1 and l < len(drop) and drop[l] is not None:
+            # dropout after the activation of a hidden layer: multipliers 0 or 1 / (1 - p)
+            A = A * np.asarray(drop[l], dtype=np.float64)
         acts.append(A)
         caches.append(cache)
     return acts, caches, (dst, src)
 
 
-def epoch(rowptr, colidx, dims, X, weights, labels, mask, relu_on=None):
+def epoch(rowptr, colidx, dims, X, weights, labels, mask, relu_on=None, drop=None):
     """One full-graph epoch.  Returns ``act``, ``loss``, ``gW``, ``ga_src``, ``ga_dst``, ``gb``
-    (lists per layer) and ``gact`` (dLoss/dA^1..dLoss/dA^L)."""
+    (lists per layer) and ``gact`` (dLoss/dA^1..dLoss/dA^L).  ``drop``: optional list with one
+    ``[n, d_l]`` array of dropout multipliers (0 or 1 / (1 - p)) or None per hidden layer, applied
+    after the activation (``act`` then holds the activations after dropout, ``gact`` the gradient
+    with respect to them)."""
     n = len(rowptr) - 1
     L = len(dims) - 1
-    acts, caches, (dst, src) = forward(rowptr, colidx, dims, X, weights)
+    acts, caches, (dst, src) = forward(rowptr, colidx, dims, X, weights, drop=drop)
     lossv, G = fullgraph.loss(acts[-1], labels, mask)
     out = {"act": acts, "loss": lossv, "gW": [None] * L, "ga_src": [None] * L, "ga_dst": [None] * L,
            "gb": [None] * L, "gact": [None] * L}
     for l in range(L - 1, -1, -1):
         out["gact"][l] = G
         if l < L - 1:
-            on = (acts[l] > 0) if relu_on is None or relu_on[l] is None else (np.asarray(relu_on[l]) != 0)
+            on = caches[l]["on"] if relu_on is None or relu_on[l] is None else (np.asarray(relu_on[l]) != 0)
             dY = G * on
+            if drop is not None and l < len(drop) and drop[l] is not None:
+                dY = dY * np.asarray(drop[l], dtype=np.float64)
         else:
             dY = G
         w = weights[l]
@@ -141,3 +150,37 @@ def epoch(rowptr, colidx, dims, X, weights, labels, mask, relu_on=None):
         G = g["gA"]
     out["gX"] = G
     return out
+
+
+def train(rowptr, colidx, dims, X, weights, labels, mask, epochs, optimizer="adam", lr=0.01, beta1=0.9,
+          beta2=0.999, eps=1e-8, weight_decay=0.0, dropout=0.0, seed=0, first_epoch=0):
+    """``epochs`` training epochs of the attention model: forward with dropout on the hidden
+    activations (the multipliers of ``fullgraph.dropout_multipliers``), loss, backward, one
+    optimizer step (``fullgraph.adam_step`` / ``sgd_step``) on W, the two attention vectors and
+    the bias of every layer.  Returns the losses, the final weights (the layout of ``weights``)
+    and the last epoch's results."""
+    L = len(dims) - 1
+    n = len(rowptr) - 1
+    keys = ("W", "a_src", "a_dst", "b")
+    cur = [{k: (None if w.get(k) is None else np.asarray(w[k], dtype=np.float64).copy()) for k in keys}
+           for w in weights]
+    heads = [int(w.get("heads", 1)) for w in weights]
+    flat = lambda ws: [w[k] for w in ws for k in keys]
+    m = [None if t is None else np.zeros_like(t) for t in flat(cur)]
+    v = [None if t is None else np.zeros_like(t) for t in flat(cur)]
+    losses, last = [], None
+    for e in range(epochs):
+        ep = first_epoch + e
+        drop = None
+        if dropout > 0:
+            drop = [fullgraph.dropout_multipliers(n, dims[l + 1], dropout, seed, ep, l + 1) for l in range(L - 1)]
+        seen = [dict(w, heads=h) for w, h in zip(cur, heads)]
+        last = epoch(rowptr, colidx, dims, X, seen, labels, mask, drop=drop)
+        losses.append(last["loss"])
+        grads = [t for l in range(L) for t in (last["gW"][l], last["ga_src"][l], last["ga_dst"][l], last["gb"][l])]
+        if optimizer == "adam":
+            new, m, v = fullgraph.adam_step(flat(cur), grads, m, v, ep + 1, lr, beta1, beta2, eps, weight_decay)
+        else:
+            new = fullgraph.sgd_step(flat(cur), grads, lr, weight_decay)
+        cur = [dict(zip(keys, new[4 * l:4 * l + 4])) for l in range(L)]
+    return losses, [dict(w, heads=h) for w, h in zip(cur, heads)], last

@@ -168,14 +168,12 @@ def test_sampled_row_check_agrees_with_the_whole_graph_epoch(heads):
 
 # ---- several attention heads -----------------------------------------------------------------
 
-def torch_dense_epoch_heads(rowptr, colidx, dims, X, w, heads, y, m):
-    """The multi-head layer written head by head on dense [n, n] attention matrices (each head
-    owns a column slice of H and of the attention vectors, the heads' outputs are concatenated),
-    differentiated by autograd."""
-    M = torch.tensor(dense_mask(rowptr, colidx))
+def torch_dense_loss(M, dims, X, params, heads, y, m, drop=None):
+    """Loss of the multi-head model written head by head on dense [n, n] attention matrices (each
+    head owns a column slice of H and of the attention vectors, the heads' outputs are
+    concatenated), as a torch graph over ``params``; ``drop``: multipliers after the hidden
+    activations.  Returns the loss tensor and the activations."""
     A = torch.tensor(X, dtype=torch.float64)
-    params = [{k: torch.tensor(v, dtype=torch.float64, requires_grad=True)
-               for k, v in wl.items() if k != "heads"} for wl in w]
     acts = []
     L = len(dims) - 1
     for l in range(L):
@@ -191,10 +189,24 @@ def torch_dense_epoch_heads(rowptr, colidx, dims, X, w, heads, y, m):
             outs.append(torch.softmax(e, dim=1) @ Hj)
         Y = torch.cat(outs, dim=1) + p["b"]
         A = torch.relu(Y) if l < L - 1 else Y
+        if drop is not None and l < L - 1:
+            A = A * torch.tensor(drop[l], dtype=torch.float64)
         A.retain_grad()
         acts.append(A)
     idx = torch.tensor(np.flatnonzero(m))
     loss = torch.nn.functional.cross_entropy(acts[-1][idx], torch.tensor(y[m != 0].astype(np.int64)))
+    return loss, acts
+
+
+def torch_params(w):
+    return [{k: torch.tensor(v, dtype=torch.float64, requires_grad=True)
+             for k, v in wl.items() if k != "heads"} for wl in w]
+
+
+def torch_dense_epoch_heads(rowptr, colidx, dims, X, w, heads, y, m, drop=None):
+    M = torch.tensor(dense_mask(rowptr, colidx))
+    params = torch_params(w)
+    loss, acts = torch_dense_loss(M, dims, X, params, heads, y, m, drop=drop)
     loss.backward()
     return loss.item(), acts, params
 
@@ -267,3 +279,57 @@ def test_multi_head_gradients_match_finite_differences():
                 arr[idx] = old
                 worst = max(worst, abs((lp - lm) / (2 * h) - g[idx]) / np.abs(g).max())
     assert worst < 1e-6, worst
+
+
+def test_dropout_after_hidden_activations_equals_autograd_of_the_dense_definition():
+    n, dims, heads = 40, (6, 12, 10, 4), (3, 1, 2)
+    rowptr, colidx, X, y, m, w = make(n, dims, seed=17)
+    for wl, h in zip(w, heads):
+        wl["heads"] = h
+    drop = [og.dropout_multipliers(n, dims[l + 1], 0.4, 5, 2, l + 1) for l in range(2)]
+    assert all(0.2 < (d == 0).mean() < 0.6 for d in drop)
+    out = gat.epoch(rowptr, colidx, dims, X, w, y, m, drop=drop)
+    loss, acts, params = torch_dense_epoch_heads(rowptr, colidx, dims, X, w, heads, y, m, drop=drop)
+    assert abs(out["loss"] - loss) < 1e-12
+    for l in range(3):
+        assert np.abs(out["act"][l] - acts[l].detach().numpy()).max() < 1e-12
+        assert np.abs(out["gact"][l] - acts[l].grad.numpy()).max() < 1e-12
+        for ours, name in (("gW", "W"), ("ga_src", "a_src"), ("ga_dst", "a_dst"), ("gb", "b")):
+            ref = params[l][name].grad.numpy()
+            assert np.abs(out[ours][l] - ref).max() < 1e-11 * max(1.0, np.abs(ref).max()), (l, name)
+    # without multipliers nothing changes
+    plain = gat.epoch(rowptr, colidx, dims, X, w, y, m)
+    again = gat.epoch(rowptr, colidx, dims, X, w, y, m, drop=[None, None])
+    assert plain["loss"] == again["loss"]
+
+
+@pytest.mark.parametrize("opt,dropout", [("adam", 0.0), ("sgd", 0.0), ("adam", 0.3)])
+def test_training_epochs_follow_a_library_optimizer_on_the_dense_definition(opt, dropout):
+    """gat.train against torch.optim (Adam with L2 weight decay / SGD) stepping the dense
+    definition's parameters; with dropout the torch model takes the same multipliers."""
+    n, dims, heads, epochs, lr, wd = 30, (5, 8, 6, 3), (2, 3, 1), 3, 0.02, 0.01
+    rowptr, colidx, X, y, m, w = make(n, dims, seed=23)
+    for wl, h in zip(w, heads):
+        wl["heads"] = h
+    losses, final, last = gat.train(rowptr, colidx, dims, X, w, y, m, epochs, optimizer=opt, lr=lr,
+                                    weight_decay=wd, dropout=dropout, seed=11, first_epoch=0)
+    M = torch.tensor(dense_mask(rowptr, colidx))
+    params = torch_params(w)
+    flat = [p[k] for p in params for k in ("W", "a_src", "a_dst", "b")]
+    optim = (torch.optim.Adam(flat, lr=lr, weight_decay=wd) if opt == "adam"
+             else torch.optim.SGD(flat, lr=lr, weight_decay=wd))
+    for e in range(epochs):
+        drop = None
+        if dropout > 0:
+            drop = [og.dropout_multipliers(n, dims[l + 1], dropout, 11, e, l + 1) for l in range(2)]
+        optim.zero_grad()
+        loss, _ = torch_dense_loss(M, dims, X, params, heads, y, m, drop=drop)
+        loss.backward()
+        assert abs(losses[e] - loss.item()) < 1e-10, (e, losses[e], loss.item())
+        optim.step()
+    assert losses[0] != losses[1]
+    for l in range(3):
+        for k in ("W", "a_src", "a_dst", "b"):
+            ref = params[l][k].detach().numpy()
+            assert np.abs(final[l][k] - ref).max() < 1e-9 * max(1.0, np.abs(ref).max()), (l, k)
+        assert final[l]["heads"] == heads[l]
