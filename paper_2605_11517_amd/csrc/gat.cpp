@@ -202,6 +202,8 @@ void gat_layer_fwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
         Timed t(c, s, GNN_K_GEMM_FWD);
         launch_add_padded(out, Z, v0.np, v0.dout, v0.dout, bias, 0, relu, s);
     }
+    Timed t(c, s, GNN_K_OTHER);
+    apply_dropout(c, layer, v0.r0, v0.np, out, 0, s);       // after the activation of a hidden layer
 }
 
 // first partition of a layer's backward pass: the accumulators start from zero
@@ -229,8 +231,10 @@ void gat_layer_bwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
     {
         Timed t(c, s, GNN_K_ACT_BWD);
         if (layer < c->L) {
+            // (dropout followed the activation: its dropped elements are the zeros of the stored
+            // rows, the others carry the factor 1 / (1 - p))
             launch_act_bwd(g_own, (const float*)c->act[(size_t)layer - 1] + v0.r0 * v0.dout, dYbuf, v0.np, v0.dout, gb,
-                           colpart, 1.f, s);
+                           colpart, c->dropout_p > 0.f ? 1.f / (1.f - c->dropout_p) : 1.f, s);
             dY = dYbuf;
         } else {
             launch_act_bwd(g_own, nullptr, nullptr, v0.np, v0.dout, gb, colpart, 1.f, s);

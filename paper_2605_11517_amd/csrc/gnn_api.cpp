@@ -442,6 +442,17 @@ static inline uint64_t splitmix64(uint64_t x)
     return z ^ (z >> 31);
 }
 
+// Dropout after the activation of hidden layer `layer` on `rows` output rows starting at library
+// row r0 (nothing when the rate is zero or the layer is the output layer).
+void apply_dropout(gnn_ctx* c, int32_t layer, int64_t r0, int64_t rows, void* out_own, int is_bf16, hipStream_t s)
+{
+    if (!(c->dropout_p > 0.f) || layer >= c->L) return;
+    const uint64_t key = splitmix64(c->dropout_seed ^ splitmix64((uint64_t)(64 * c->dropout_epoch + layer)));
+    const uint32_t threshold = (uint32_t)std::floor((double)c->dropout_p * 4294967296.0);
+    launch_dropout(out_own, is_bf16, c->D.order + r0, rows, c->dims[(size_t)layer], key, threshold,
+                   1.f / (1.f - c->dropout_p), s);
+}
+
 void compute_fwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, char* out_own, hipStream_t s)
 {
     const HostMeta& M = c->M;

@@ -299,6 +299,9 @@ void xf_transform_bwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, 
 void zero_weight_grads(gnn_ctx* c, hipStream_t s);
 SpmmItems plan_items(const HostMeta::Plan& H, const DevMeta::Plan& P, int32_t p);
 
+// dropout after the activation of a hidden layer on the rows [r0, r0 + rows) (no-op when off)
+void apply_dropout(gnn_ctx* c, int32_t layer, int64_t r0, int64_t rows, void* out_own, int is_bf16, hipStream_t s);
+
 // gat.cpp: the steps of a graph-attention layer for one partition
 void gat_transform_fwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s);
 void gat_gather(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s);

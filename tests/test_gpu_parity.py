@@ -1329,6 +1329,64 @@ def test_multi_head_attention_epoch_matches_oracle(name, dims, heads, k, mode):
     assert abs(l1 - ref1["loss"]) <= TOL * abs(ref1["loss"])
 
 
+@pytest.mark.parametrize("dims,heads,dropout", [((12, 24, 16, 5), (1, 1, 1), 0.3),
+                                                ((12, 32, 24, 6), (4, 3, 2), 0.4),
+                                                ((12, 32, 24, 6), (4, 3, 2), 0.0)])
+def test_attention_dropout_epoch_and_training_steps_match_oracle(dims, heads, dropout):
+    """Graph attention under training: one epoch with dropout after the hidden activations (the
+    same elements dropped as in the oracle, every array compared), then three epochs with an
+    optimizer step each (Adam, SGD; W, both attention vectors and the bias) against the oracle's
+    training loop."""
+    say("case attention training %s heads %s dropout %g" % (dims, heads, dropout))
+    from oracle import gat as ogat
+    from paper_2605_11517_amd import Session
+    n, k, seed = 1500, 5, 17
+    rowptr, colidx = small_graph(n, 9000, seed=3, symmetric=True, self_loops=False)
+    L = len(dims) - 1
+    X = features(n, dims[0], seed)
+    y, m = labels_and_mask(n, dims[-1], 0.6, seed)
+    w = gat_weights(dims, seed)
+    for wl, h in zip(w, heads):
+        wl["heads"] = h
+
+    def check(got, ref, tag):
+        worst = {}
+        for l in range(L):
+            worst["act[%d]" % l] = rel_err(got["act"][l], ref["act"][l])
+            worst["gact[%d]" % l] = rel_err(got["gact"][l], ref["gact"][l])
+            worst["gW[%d]" % l] = rel_err(got["gW"][l], ref["gW"][l])
+            worst["ga[%d]" % l] = rel_err(got["gWs"][l], np.stack([ref["ga_src"][l], ref["ga_dst"][l]]))
+            worst["gb[%d]" % l] = rel_err(got["gb"][l], ref["gb"][l])
+        bad = {key: v for key, v in worst.items() if not (v <= TOL)}
+        assert not bad, (tag, bad)
+
+    s = Session("gat", dims, rowptr, colidx, k, "switching", seed, X, w, y, m, fuse_gather=True)
+    s.ctx.set_dropout(dropout, 99, 4)
+    loss = s.epoch()
+    got = s.results()
+    drop = None
+    if dropout > 0:
+        drop = [og.dropout_multipliers(n, dims[l + 1], dropout, 99, 4, l + 1) for l in range(L - 1)]
+        for l in range(L - 1):          # the same elements are dropped, bit for bit
+            assert np.all(got["act"][l][drop[l] == 0] == 0)
+    ref = ogat.epoch(rowptr, colidx, dims, X, w, y, m, drop=drop)
+    assert abs(loss - ref["loss"]) <= TOL * abs(ref["loss"])
+    check(got, ref, "dropout epoch")
+    for opt, lr in (("adam", 0.01), ("sgd", 0.05)):
+        s = Session("gat", dims, rowptr, colidx, k, "lp", seed, X, w, y, m)
+        losses = s.train(3, optimizer=opt, lr=lr, weight_decay=0.01, dropout=dropout, seed=7)
+        ref_losses, ref_w, _ = ogat.train(rowptr, colidx, dims, X, w, y, m, epochs=3, optimizer=opt, lr=lr,
+                                          weight_decay=0.01, dropout=dropout, seed=7)
+        for a, b in zip(losses, ref_losses):
+            assert abs(a - b) <= TOL * abs(b), (opt, losses, ref_losses)
+        gw = s.weights()
+        for l in range(L):
+            assert rel_err(gw[l]["W"], ref_w[l]["W"]) <= TOL, (opt, l, "W")
+            assert rel_err(gw[l]["Ws"], np.stack([ref_w[l]["a_src"], ref_w[l]["a_dst"]])) <= TOL, (opt, l, "a")
+            assert rel_err(gw[l]["b"], ref_w[l]["b"]) <= TOL, (opt, l, "b")
+        say("  %s losses %s" % (opt, ["%.5f" % x for x in losses]))
+
+
 # ----------------------------------------------------------------------------------------
 # measurement hooks
 # ----------------------------------------------------------------------------------------
