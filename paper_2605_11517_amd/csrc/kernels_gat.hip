@@ -300,6 +300,179 @@ __device__ inline void bwd_row_wave(const GatRows& g, int32_t row, int32_t h0, c
     }
 }
 
+// Rows of at most kGroupRow entries: a group of 16 lanes per row, four rows of the range item
+// at a time (a wavefront that walks its rows one after the other waits three dependent memory
+// round trips per row - row pointer, columns, scores - with nothing else in flight).  Every lane
+// of the wavefront runs the same number of row steps; lanes without a row take an empty one.
+constexpr int kGroup = 16;
+constexpr int kGroupRow = kGroup * kPerLane;      // 128 entries
+
+template <int HB, bool VEC>
+__device__ inline void att_rows_groups(const GatRows& g, int32_t r0, int32_t r1, float* __restrict__ att_all)
+{
+    const int lane = threadIdx.x % kWave, gl = lane % kGroup, grp = lane / kGroup;
+    for (int32_t i0 = r0; i0 < r1; i0 += kWave / kGroup) {
+        const int32_t row = i0 + grp;
+        int64_t eb = 0, ee = 0;
+        if (row < r1) {
+            eb = g.rp[row];
+            ee = g.rp[row + 1];
+            if (ee - eb > kGroupRow) ee = eb;           // longer rows: a whole wavefront each, afterwards
+        }
+        const int niter = (int)((ee - eb + kGroup - 1) / kGroup);
+        int32_t cols[kPerLane];
+#pragma unroll
+        for (int i = 0; i < kPerLane; ++i) {
+            const int64_t e = eb + gl + (int64_t)i * kGroup;
+            cols[i] = e < ee ? g.col[e] : -1;
+        }
+        for (int32_t h0 = 0; h0 < g.nh; h0 += HB) {
+            const int nhb = g.nh - h0 < HB ? g.nh - h0 : HB;
+            float sd[HB], m[HB], sum[HB];
+#pragma unroll
+            for (int b = 0; b < HB; ++b) {
+                sd[b] = (b < nhb && row < r1) ? g.sdst_own[(int64_t)row * g.nh + h0 + b] : 0.f;
+                m[b] = -INFINITY;
+                sum[b] = 0.f;
+            }
+            float x[HB][kPerLane];
+#pragma unroll
+            for (int i = 0; i < kPerLane; ++i) {
+#pragma unroll
+                for (int b = 0; b < HB; ++b) x[b][i] = -INFINITY;
+                if (i < niter && cols[i] >= 0) {
+                    float sc[HB];
+                    load_scores<HB, VEC>(g, cols[i], h0, nhb, sc);
+#pragma unroll
+                    for (int b = 0; b < HB; ++b) x[b][i] = lrelu(sc[b] + sd[b]);
+                }
+#pragma unroll
+                for (int b = 0; b < HB; ++b) m[b] = fmaxf(m[b], x[b][i]);
+            }
+#pragma unroll
+            for (int b = 0; b < HB; ++b) {
+#pragma unroll
+                for (int k = 1; k < kGroup; k <<= 1) m[b] = fmaxf(m[b], __shfl_xor(m[b], k, kWave));
+            }
+#pragma unroll
+            for (int i = 0; i < kPerLane; ++i)
+                if (i < niter) {
+#pragma unroll
+                    for (int b = 0; b < HB; ++b) {
+                        x[b][i] = expf(x[b][i] - m[b]);      // exp(-inf) = 0 past the row end
+                        sum[b] += x[b][i];
+                    }
+                }
+#pragma unroll
+            for (int b = 0; b < HB; ++b) {
+#pragma unroll
+                for (int k = 1; k < kGroup; k <<= 1) sum[b] += __shfl_xor(sum[b], k, kWave);
+                sum[b] = 1.f / sum[b];
+            }
+#pragma unroll
+            for (int i = 0; i < kPerLane; ++i)
+                if (i < niter && cols[i] >= 0) {
+                    const int64_t e = eb + gl + (int64_t)i * kGroup;
+#pragma unroll
+                    for (int b = 0; b < HB; ++b)
+                        if (b < nhb) att_all[(h0 + b) * g.hs + (e - g.e0)] = x[b][i] * sum[b];
+                }
+        }
+    }
+}
+
+// The backward scalars of such rows, the same way (see bwd_row_wave for what is computed).
+template <int HB, bool VEC>
+__device__ inline void bwd_rows_groups(const GatRows& g, int32_t r0, int32_t r1, const float* __restrict__ att_all,
+                                       const float* __restrict__ dal_all, float* __restrict__ pair,
+                                       float* __restrict__ gs_dst_own)
+{
+    const int lane = threadIdx.x % kWave, gl = lane % kGroup, grp = lane / kGroup;
+    for (int32_t i0 = r0; i0 < r1; i0 += kWave / kGroup) {
+        const int32_t row = i0 + grp;
+        int64_t eb = 0, ee = 0;
+        if (row < r1) {
+            eb = g.rp[row];
+            ee = g.rp[row + 1];
+            if (ee - eb > kGroupRow) ee = eb;           // longer rows: a whole wavefront each, afterwards
+        }
+        const int niter = (int)((ee - eb + kGroup - 1) / kGroup);
+        int32_t cols[kPerLane];
+#pragma unroll
+        for (int i = 0; i < kPerLane; ++i) {
+            const int64_t e = eb + gl + (int64_t)i * kGroup;
+            cols[i] = e < ee ? g.col[e] : -1;
+        }
+        for (int32_t h0 = 0; h0 < g.nh; h0 += HB) {
+            const int nhb = g.nh - h0 < HB ? g.nh - h0 : HB;
+            float sd[HB], tv[HB], ds[HB];
+            unsigned pos[HB];
+#pragma unroll
+            for (int b = 0; b < HB; ++b) {
+                sd[b] = (b < nhb && row < r1) ? g.sdst_own[(int64_t)row * g.nh + h0 + b] : 0.f;
+                tv[b] = 0.f;
+                ds[b] = 0.f;
+                pos[b] = 0u;
+            }
+            float a[HB][kPerLane], d[HB][kPerLane];
+#pragma unroll
+            for (int i = 0; i < kPerLane; ++i) {
+#pragma unroll
+                for (int b = 0; b < HB; ++b) { a[b][i] = 0.f; d[b][i] = 0.f; }
+                if (i < niter && cols[i] >= 0) {
+                    const int64_t e = eb + gl + (int64_t)i * kGroup;
+                    float sc[HB];
+                    load_scores<HB, VEC && HB == 4>(g, cols[i], h0, nhb, sc);
+#pragma unroll
+                    for (int b = 0; b < HB; ++b)
+                        if (b < nhb) {
+                            a[b][i] = att_all[(h0 + b) * g.hs + (e - g.e0)];
+                            d[b][i] = dal_all[(h0 + b) * g.hs + (e - g.e0)];
+                            if (sc[b] + sd[b] > 0.f) pos[b] |= 1u << i;
+                        }
+                }
+#pragma unroll
+                for (int b = 0; b < HB; ++b) tv[b] += a[b][i] * d[b][i];
+            }
+#pragma unroll
+            for (int b = 0; b < HB; ++b) {
+#pragma unroll
+                for (int k = 1; k < kGroup; k <<= 1) tv[b] += __shfl_xor(tv[b], k, kWave);
+            }
+#pragma unroll
+            for (int i = 0; i < kPerLane; ++i)
+                if (i < niter) {
+                    float dp[HB];
+#pragma unroll
+                    for (int b = 0; b < HB; ++b) {
+                        dp[b] = a[b][i] * (d[b][i] - tv[b]) * ((pos[b] >> i) & 1u ? 1.f : kSlope);
+                        ds[b] += dp[b];
+                    }
+                    if (cols[i] >= 0) {
+                        const int64_t e = eb + gl + (int64_t)i * kGroup;
+                        float* q = pair + ((e - g.e0) * g.nh + h0) * 2;
+                        if (VEC) {
+#pragma unroll
+                            for (int b = 0; b + 1 < HB; b += 2)
+                                *reinterpret_cast<float4*>(q + 2 * b) =
+                                    make_float4(a[b][i], dp[b], a[b + 1][i], dp[b + 1]);
+                        } else {
+#pragma unroll
+                            for (int b = 0; b < HB; ++b)
+                                if (b < nhb) *reinterpret_cast<float2*>(q + 2 * b) = make_float2(a[b][i], dp[b]);
+                        }
+                    }
+                }
+#pragma unroll
+            for (int b = 0; b < HB; ++b) {
+#pragma unroll
+                for (int k = 1; k < kGroup; k <<= 1) ds[b] += __shfl_xor(ds[b], k, kWave);
+                if (gl == 0 && b < nhb && ee > eb) gs_dst_own[(int64_t)row * g.nh + h0 + b] = ds[b];
+            }
+        }
+    }
+}
+
 // MODE 0: attention weights; MODE 1: backward scalars.  One range item of short rows per
 // wavefront; long rows are skipped here and handled segment by segment below.
 template <int MODE, int HB, bool VEC>
@@ -310,8 +483,11 @@ __global__ __launch_bounds__(kBlock) void k_gat_rows(const GatRows g, float* __r
     const int64_t item = (int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;
     if (item >= g.nranges) return;
     const int32_t r1 = g.range_rows[item + 1];
+    if constexpr (MODE == 0) att_rows_groups<HB, VEC>(g, g.range_rows[item], r1, att);
+    else bwd_rows_groups<HB, VEC>(g, g.range_rows[item], r1, att, dal, pair, gs_dst_own);
     for (int32_t row = g.range_rows[item]; row < r1; ++row) {
-        if (g.rp[row + 1] - g.rp[row] > kSpmmSegment) continue;
+        const int64_t len = g.rp[row + 1] - g.rp[row];
+        if (len > kSpmmSegment || len <= kGroupRow) continue;
         for (int32_t h0 = 0; h0 < g.nh; h0 += HB) {
             if constexpr (MODE == 0) att_row_wave<HB, VEC>(g, row, h0, att);
             else bwd_row_wave<HB, VEC>(g, row, h0, att, dal, pair, gs_dst_own);

@@ -265,16 +265,22 @@ def gat_sampled_errors(rowptr, colidx, dims, weights, X, act, gact, gb, V, say=N
         worst["act[%d] rows" % (l - 1)] = rel_err(np.asarray(A[l])[V], np.array(ref))
 
         # per-vertex softmax statistics over all edges, then the input gradient of sampled rows
+        # (the entries are the CSR's, row by row, followed by one self-loop per vertex in vertex
+        # order: per-row maxima and sums are segment reductions plus the self-loop's term)
         mx = np.full((n, nh), -np.inf)
         den = np.zeros((n, nh))
+        nnz = int(rowptr[-1])
+        has = deg > 0
+        starts = np.asarray(rowptr[:-1])[has]
         for j in range(nh):
             e = leaky(s_src[src, j] + s_dst[dst, j])
-            m1 = np.full(n, -np.inf)
-            np.maximum.at(m1, dst, e)
-            d1 = np.zeros(n)
-            np.add.at(d1, dst, np.exp(e - m1[dst]))
+            m1 = e[nnz:].copy()
+            m1[has] = np.maximum(m1[has], np.maximum.reduceat(e[:nnz], starts))
+            ex = np.exp(e - m1[dst])
+            d1 = ex[nnz:].copy()
+            d1[has] += np.add.reduceat(ex[:nnz], starts)
             mx[:, j], den[:, j] = m1, d1
-            del e
+            del e, ex
         dY = np.asarray(gact[l - 1], dtype=np.float64)
         if l < L:
             dY = np.where(np.asarray(A[l]) > 0, dY, 0.0)
