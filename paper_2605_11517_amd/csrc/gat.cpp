@@ -105,6 +105,8 @@ GatRowsHost rows_of(gnn_ctx* c, const GatView& v, int32_t p)
     h.nh = v.nh;
     h.hs = v.hs;
     h.items = plan_items(c->M.plan_fwd, c->D.fwd, p);
+    // entries per row: the aggregation launchers pick their short-row kernels by it
+    h.items.avg_len = (float)(c->M.rp[(size_t)(v.r0 + v.np)] - v.e0) / (float)std::max<int64_t>(1, v.np);
     return h;
 }
 
@@ -241,7 +243,9 @@ void gat_layer_bwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
         }
     }
     const int64_t t0 = M.toff[(size_t)p];
-    const SpmmItems titems = plan_items(M.plan_bwd, c->D.bwd, p);
+    SpmmItems titems = plan_items(M.plan_bwd, c->D.bwd, p);
+    titems.avg_len = (float)(M.trp[(size_t)M.toff[(size_t)p + 1]] - M.trp[(size_t)t0]) /
+                     (float)std::max<int64_t>(1, v0.np + v0.nb);
     const int32_t* bnd = c->D.bnd + M.boff[(size_t)p];
     float* segpart = (float*)(c->scratch + c->ws.segpart);
     const GatRowsHost rows = rows_of(c, v0, p);
