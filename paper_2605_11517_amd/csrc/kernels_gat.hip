@@ -577,7 +577,7 @@ __global__ __launch_bounds__(kBlock) void k_gat_segments(const GatRows g, const 
             }
         }
     } else if constexpr (STEP == 3) {
-        static_assert(STEP != 3 || HB <= 2, "pairs of one or two heads");
+        static_assert(STEP != 3 || HB == 1 || HB == 2 || HB == 4, "blocks of one, two or four heads");
         for (int32_t h0 = 0; h0 < g.nh; h0 += HB) {
             const int nhb = g.nh - h0 < HB ? g.nh - h0 : HB;
             float sd[HB], tv[HB], ds[HB];
@@ -592,7 +592,7 @@ __global__ __launch_bounds__(kBlock) void k_gat_segments(const GatRows g, const 
                 const int64_t e = eb + t + (int64_t)i * kWave;
                 if (e < ee) {
                     float sc[HB], av[HB], dp[HB];
-                    load_scores<HB, false>(g, g.col[e], h0, nhb, sc);
+                    load_scores<HB, VEC && HB == 4>(g, g.col[e], h0, nhb, sc);
 #pragma unroll
                     for (int b = 0; b < HB; ++b) {
                         av[b] = 0.f; dp[b] = 0.f;
@@ -604,8 +604,10 @@ __global__ __launch_bounds__(kBlock) void k_gat_segments(const GatRows g, const 
                         }
                     }
                     float* qp = pair + ((e - g.e0) * g.nh + h0) * 2;
-                    if (HB == 2 && VEC) {
-                        *reinterpret_cast<float4*>(qp) = make_float4(av[0], dp[0], av[HB - 1], dp[HB - 1]);
+                    if (VEC) {          // whole blocks of an even number of heads: 16-byte stores
+#pragma unroll
+                        for (int b = 0; b + 1 < HB; b += 2)
+                            *reinterpret_cast<float4*>(qp + 2 * b) = make_float4(av[b], dp[b], av[b + 1], dp[b + 1]);
                     } else {
 #pragma unroll
                         for (int b = 0; b < HB; ++b)
@@ -1075,6 +1077,8 @@ void launch_gat_bwd_scalars(const GatRowsHost& h, const float* att, const float*
         hipLaunchKernelGGL((k_gat_combine<2>), gl, b, 0, s, q, g.nh, (const float*)stat, factor, none);
         if (g.nh == 1)
             hipLaunchKernelGGL((k_gat_segments<3, 1, false>), gs, b, 0, s, g, q, a, d, stat, (const float*)factor, pair);
+        else if (g.nh % 4 == 0)
+            hipLaunchKernelGGL((k_gat_segments<3, 4, true>), gs, b, 0, s, g, q, a, d, stat, (const float*)factor, pair);
         else if (g.nh % 2 == 0)
             hipLaunchKernelGGL((k_gat_segments<3, 2, true>), gs, b, 0, s, g, q, a, d, stat, (const float*)factor, pair);
         else
