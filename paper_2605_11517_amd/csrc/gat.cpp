@@ -3,7 +3,9 @@
 // the model family the paper evaluates next to GCN and GraphSAGE; its section on activation
 // regathering notes that attention needs the gathered inputs themselves in the backward pass).
 //
-// A layer always transforms first.  Forward: sweep 1 computes H_p = A_p^{l-1} W and the scores
+// A layer always transforms first.  (With the gather fused into the kernels, see GatView, the
+// gathers below move nothing and the kernels read the same rows and scores where they lie.)
+// Forward: sweep 1 computes H_p = A_p^{l-1} W and the scores
 // s_src = H a_src, s_dst = H a_dst for every partition; sweep 2, per partition, gathers the rows
 // of H and the scores s_src of the boundary vertices, turns the scores into attention weights
 // (softmax over each destination's sources of LeakyReLU(s_src + s_dst)) and aggregates H with

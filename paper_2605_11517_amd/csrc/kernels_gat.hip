@@ -9,12 +9,13 @@
 // Several heads: the per-vertex scores of all heads of a vertex lie side by side (nh floats per
 // vertex, so one fetch of a neighbour's scores serves every head), the per-entry arrays (attention
 // weights, edge-wise products) are kept head after head, `hs` floats apart, and the row-wise
-// passes walk the heads of a row one after the other.
+// passes take the heads of a row in blocks of up to four.
 //
-// Row-wise scalar passes: a wavefront walks the short rows of a range item one after the other;
-// long rows are cut into the aggregation kernel's segments, one wavefront per segment, and
-// combined per row in segment order.  All reductions are shuffles and fixed-order sums, so
-// results are reproducible.
+// Row-wise scalar passes: a wavefront takes a range item of short rows - rows of up to 128
+// entries four at a time, a group of 16 lanes each, longer ones one after the other with the
+// whole wavefront; long rows (more than 512 entries) are cut into the aggregation kernel's
+// segments, one wavefront per segment, and combined per row in segment order.  All reductions
+// are shuffles and fixed-order sums, so results are reproducible.
 #include "gnn_internal.h"
 
 namespace gnnmi {
@@ -693,8 +694,6 @@ struct GatTRows {
     int64_t hs;                 // tw_att one array per head, hs floats apart
     const int32_t* range_rows;
     int64_t nranges;
-    const int32_t* long_row;
-    int64_t nlong;
 };
 // Long transposed rows (a hub as a source: up to 10^5 destinations in one partition) are cut
 // into the aggregation's segments like the long forward rows: one wavefront per segment and all
@@ -1095,7 +1094,6 @@ void launch_gat_transposed(const int64_t* trp, const int32_t* tperm, int64_t e0,
     g.trp = trp; g.tperm = tperm; g.e0 = e0; g.n_own = n_own; g.base_row = base_row; g.bnd = bnd;
     g.nh = nh; g.hs = hs;
     g.range_rows = items.range_rows; g.nranges = items.nranges;
-    g.long_row = items.long_row; g.nlong = items.nlong;
     if (g.nranges > 0) {
         const dim3 grid((unsigned)((g.nranges + 3) / 4)), b(kBlock);
         if (nh % 2 == 0) hipLaunchKernelGGL((k_gat_trows<true>), grid, b, 0, s, g, pair, tw_att, gs_src);
