@@ -1270,6 +1270,8 @@ def test_graph_attention_epoch_matches_oracle(name, dims, k, mode):
     ("mini_sage", (24, 256, 7), (4, 1), 1, "random"),                    # 64-column heads, k = 1
     ("tiny", (64, 64, 32), (4, 2), 4, "switching"),                      # 16-column heads in one aggregation launch, hub rows, boundary rows
     ("mini_sage", (24, 128, 64, 7), (4, 2, 1), 5, "lp"),                 # 32-column heads in one launch
+    ("tiny", (64, 256, 16), (2, 1), 4, "lp"),                            # 128-column heads in one launch, hub rows
+    ("mini_gcn_directed", (20, 48, 7), (6, 1), 7, "random"),             # six heads: a last block of two
 ])
 def test_multi_head_attention_epoch_matches_oracle(name, dims, heads, k, mode):
     """Several attention heads per layer (gnn_set_gat_heads): every array of the epoch against the
