@@ -170,41 +170,49 @@ void gat_layer_fwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
     const float* bias = c->has_bias ? (const float*)c->w[(size_t)3 * (layer - 1) + 2] : nullptr;
     float* out = (float*)c->act[(size_t)layer - 1] + v0.r0 * v0.dout;
     const int relu = layer < c->L ? 1 : 0;
+    // Rows of H as wide as the output rows (heads side by side, or one head of unpadded width): the
+    // aggregation stores the layer's output itself, bias and activation where it stores a row.
+    // Otherwise it fills Z and the head's columns are copied out.
+    const bool direct = v0.ldh == v0.dout;
+    float* agg = direct ? out : Z;
+    SpmmScatter fin;                 // no scatter; what is applied to a stored row
+    if (direct) {
+        fin.bias = bias;
+        fin.relu = relu;
+    }
     // heads side by side: every head in one launch, a column slice of the rows each (when the
     // head width suits the slot kernels), else head by head
     bool all_heads = false;
     if (v0.side) {
         Timed t(c, s, GNN_K_SPMM);
         all_heads = launch_spmm_heads(rows.rp, rows.col, v0.att - v0.e0, v0.hs, nh, v0.f, v0.src, v0.n_src,
-                                      v0.bsrc, Z, v0.ldh, rows.items, segpart, SpmmScatter{}, s);
+                                      v0.bsrc, agg, v0.ldh, rows.items, segpart, fin, s);
     }
     if (all_heads && rows.items.nlong > 0) {
         Timed t(c, s, GNN_K_SPMM_REDUCE);
-        launch_spmm_reduce(nullptr, Z, v0.ldh, 0, rows.items, segpart, SpmmScatter{}, s);
+        launch_spmm_reduce(nullptr, agg, v0.ldh, 0, rows.items, segpart, fin, s);
     }
     for (int32_t h = 0; h < nh && !all_heads; ++h) {
         const GatView v = view(c, layer, p, h);
-        // Z rows like the rows of H: the head's column block, or an array of its own
-        float* Zh = Z + (v.side ? (int64_t)h * v.f : 0);
+        // the head's column block of the output rows (or of Z), or Z as an array of its own
+        float* Zh = agg + (v.side ? (int64_t)h * v.f : 0);
+        SpmmScatter finh = fin;
+        if (finh.bias) finh.bias += (int64_t)h * v.f;
         {
             Timed t(c, s, GNN_K_SPMM);
             launch_spmm(rows.rp, rows.col, v.att - v.e0, nullptr, v.src, v.n_src, v.bsrc, Zh, v.np, v.fp,
-                        0, 0, rows.items, segpart, 1, SpmmScatter{}, s, v.ldh);
+                        0, 0, rows.items, segpart, 1, finh, s, v.ldh);
         }
         if (rows.items.nlong > 0) {
             Timed t(c, s, GNN_K_SPMM_REDUCE);
-            launch_spmm_reduce(nullptr, Zh, v.fp, 0, rows.items, segpart, SpmmScatter{}, s, v.ldh);
+            launch_spmm_reduce(nullptr, Zh, v.fp, 0, rows.items, segpart, finh, s, v.ldh);
         }
-        if (!v.side) {
+        if (!direct) {
             // the head's columns of the output rows
             Timed t(c, s, GNN_K_GEMM_FWD);
             launch_add_padded(out + (int64_t)h * v.f, Z, v.np, v.f, v.fp, bias ? bias + (int64_t)h * v.f : nullptr, 0,
                               relu, s, v.dout);
         }
-    }
-    if (v0.side) {
-        Timed t(c, s, GNN_K_GEMM_FWD);
-        launch_add_padded(out, Z, v0.np, v0.dout, v0.dout, bias, 0, relu, s);
     }
     Timed t(c, s, GNN_K_OTHER);
     apply_dropout(c, layer, v0.r0, v0.np, out, 0, s);       // after the activation of a hidden layer
