@@ -226,6 +226,7 @@ def run_workload(name, args, steps, warmup, want_cpu):
     s = Session(model, dims, rowptr, colidx, cfg["k"], cfg["part"], cfg["seed"], X, w, y, m,
                 dtype=cfg["dtype"], hbm_budget_bytes=budget,
                 layer_order=args.layer_order, fuse_gather=not args.staged_gather,
+                keep_forward=(model == "gat" and not args.gat_recompute),
                 masked_backward=not args.full_backward, storage_dir=args.storage_dir,
                 host_budget_bytes=int(args.host_budget_gb * 2 ** 30), progress=lambda msg: log("  " + msg))
     if args.storage_dir and args.storage_drop_results:
@@ -368,6 +369,9 @@ def run_workload(name, args, steps, warmup, want_cpu):
                    "dims": list(dims), "k": stats["k"], "partitioner": cfg["part"],
                    "alpha": stats["sum_required"] / n, "sum_boundary": stats["sum_boundary"],
                    "layer_order": ["transform-first" if t else "aggregate-first" for t in xf],
+                   **({"attention_forward_results": "recomputed in the backward pass" if args.gat_recompute
+                       else "kept for the backward pass (H, scores, attention weights of every layer)"}
+                      if model == "gat" else {}),
                    "gather": ("fused into the aggregation (rows read from the whole-graph array through B_p)"
                               if gather_fused else "a step of its own, through the staging buffer"),
                    "output_layer_backward": ("%d operator entries of train vertices of %d (the loss gradient is "
@@ -507,6 +511,9 @@ def main():
     ap.add_argument("--graph-scale", type=float, default=1.0,
                     help="shrink the workload's graph (vertices and drawn edges) by this factor; "
                          "for runs that would not fit the host otherwise")
+    ap.add_argument("--gat-recompute", action="store_true",
+                    help="graph-attention workloads: recompute H, the scores and the attention weights in the "
+                         "backward pass (the paper's rule) instead of keeping them from the forward pass")
     ap.add_argument("--gat-heads", default=None,
                     help="graph-attention workloads: attention heads per layer, comma-separated (e.g. 8,8,1)")
     ap.add_argument("--train", action="store_true",

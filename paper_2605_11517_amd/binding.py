@@ -104,6 +104,7 @@ def load_library():
         "gnn_epoch": [vp, vp, P(C.c_float)],
         "gnn_set_layer_order": [vp, i32],
         "gnn_set_gat_heads": [vp, i32, i32],
+        "gnn_set_keep_forward": [vp, i32],
         "gnn_layer_is_transform_first": [vp, i32, P(i32)],
         "gnn_layer_transform_fwd": [vp, i32, i32, vp],
         "gnn_layer_transform_bwd": [vp, i32, i32, vp],
@@ -294,6 +295,9 @@ class Context:
     def set_gat_heads(self, layer, heads):
         self._check(self.lib.gnn_set_gat_heads(self.h, int(layer), int(heads)))
 
+    def set_keep_forward(self, on):
+        self._check(self.lib.gnn_set_keep_forward(self.h, 1 if on else 0))
+
     def layer_is_transform_first(self, layer):
         out = C.c_int32()
         self._check(self.lib.gnn_layer_is_transform_first(self.h, layer, C.byref(out)))
@@ -375,7 +379,7 @@ class Session:
     def __init__(self, model, dims, rowptr, colidx, k, part_mode, seed, X, weights, labels,
                  train_mask, has_bias=True, user_part=None, device="cuda:0", dtype="f32",
                  hbm_budget_bytes=0, layer_order="aggregate", fuse_gather=False, masked_backward=False,
-                 storage_dir=None, host_budget_bytes=0, progress=None):
+                 storage_dir=None, host_budget_bytes=0, progress=None, keep_forward=False):
         import torch
         self.torch = torch
         if not torch.cuda.is_available():
@@ -391,6 +395,7 @@ class Session:
         self.ctx.set_layer_order(layer_order)
         self.ctx.set_gather_fusion(fuse_gather)
         self.ctx.set_masked_backward(masked_backward)
+        self.ctx.set_keep_forward(keep_forward)
         if _MODEL.get(model, model) == GNN_GAT:
             # attention heads per layer: weights[l]["heads"] (default 1)
             for l, wl in enumerate(weights):

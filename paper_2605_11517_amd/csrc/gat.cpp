@@ -69,17 +69,22 @@ GatView view(gnn_ctx* c, int32_t layer, int32_t p, int32_t h)
     v.ldh = v.side ? v.dout : v.fp;
     char* sc = c->scratch;
     const int64_t hoff = v.side ? (int64_t)h * v.f : (int64_t)h * v.n * v.fp;
-    v.H = (float*)c->hbuf + hoff;
+    // forward results kept for the backward pass (gnn_set_keep_forward): H, the scores and the
+    // attention weights of every layer (and partition) have places of their own
+    const bool keep = c->keep_forward && !c->ws.gat_h_off.empty();
+    const int64_t mh = c->max_heads();
+    v.H = (float*)c->hbuf + (keep ? c->ws.gat_h_off[(size_t)layer - 1] : 0) + hoff;
     v.gH = (float*)c->ghbuf + hoff;
     // scores: element (vertex r, head h) at [r nh + h]
-    v.ssrc = (float*)(sc + c->ws.ssrc) + h;
-    v.sdst = (float*)(sc + c->ws.sdst) + h;
+    const int64_t so = keep ? (int64_t)(layer - 1) * v.n * mh : 0;
+    v.ssrc = (float*)(sc + c->ws.ssrc) + so + h;
+    v.sdst = (float*)(sc + c->ws.sdst) + so + h;
     v.gssrc = (float*)(sc + c->ws.gssrc) + h;
     v.gsdst = (float*)(sc + c->ws.gsdst) + h;
     v.bs = (float*)(sc + c->ws.bs) + h;
     v.stg = (float*)c->staging + (v.side ? (int64_t)h * v.f : (int64_t)h * v.nb * v.fp);
     v.hs = M.stats.max_nnz;
-    v.att = (float*)(sc + c->ws.att) + (int64_t)h * v.hs;
+    v.att = (float*)(sc + c->ws.att) + (keep ? ((int64_t)(layer - 1) * M.k + p) * mh * v.hs : 0) + (int64_t)h * v.hs;
     v.dal = (float*)(sc + c->ws.dal) + (int64_t)h * v.hs;
     v.twatt = (float*)(sc + c->ws.twatt) + (int64_t)h * v.hs;
     v.pair = (float*)(sc + c->ws.pair);       // (att, dpre) of every entry and head, entry-major
@@ -166,6 +171,7 @@ void gat_layer_fwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
         // attention weights of every head
         Timed t(c, s, GNN_K_OTHER);
         launch_gat_attention(rows, v0.att, segpart, s);
+        c->att_done[(size_t)(layer - 1) * (size_t)c->M.k + (size_t)p] = 1;
     }
     const float* bias = c->has_bias ? (const float*)c->w[(size_t)3 * (layer - 1) + 2] : nullptr;
     float* out = (float*)c->act[(size_t)layer - 1] + v0.r0 * v0.dout;
@@ -259,8 +265,9 @@ void gat_layer_bwd(gnn_ctx* c, int32_t layer, int32_t p, hipStream_t s)
     const int32_t* bnd = c->D.bnd + M.boff[(size_t)p];
     float* segpart = (float*)(c->scratch + c->ws.segpart);
     const GatRowsHost rows = rows_of(c, v0, p);
-    {
-        // recompute the attention weights of every head from the regathered scores
+    if (!(c->keep_forward && c->att_done[(size_t)(layer - 1) * (size_t)M.k + (size_t)p])) {
+        // recompute the attention weights of every head from the regathered scores (unless the
+        // forward pass's are kept)
         Timed t(c, s, GNN_K_OTHER);
         launch_gat_attention(rows, v0.att, segpart, s);
     }

@@ -312,8 +312,19 @@ void compute_workspace(gnn_ctx* c)
         // (Streaming schedule: these whole-graph buffers come out of the HBM budget instead, see
         // stream_engine_create.)
         w.h_floats = M.n * hp;
+        w.gat_h_off.clear();
         if (!c->streaming()) {
-            w.h = take(M.n * hp);
+            if (c->model == GNN_GAT && c->keep_forward) {
+                // one H per layer, one after the other
+                int64_t total = 0;
+                for (int32_t l = 1; l <= L; ++l) {
+                    w.gat_h_off.push_back(total);
+                    total += M.n * (int64_t)c->hrow(l);
+                }
+                w.h = take(total);
+            } else {
+                w.h = take(M.n * hp);
+            }
             w.gh = c->model == GNN_GAT ? take(M.n * hp) : w.h;
         }
         w.wpad = take(2 * din * hp);
@@ -330,12 +341,15 @@ void compute_workspace(gnn_ctx* c)
     }
     if (c->model == GNN_GAT) {
         const int64_t mh = c->max_heads();      // per-vertex scores: the heads' values side by side
-        w.ssrc = take(M.n * mh);
-        w.sdst = take(M.n * mh);
+        // (kept forward results: the scores of every layer, the attention weights of every layer
+        // and partition)
+        const int64_t keepl = c->keep_forward ? L : 1;
+        w.ssrc = take(M.n * mh * keepl);
+        w.sdst = take(M.n * mh * keepl);
         w.gssrc = take(M.n * mh);
         w.gsdst = take(M.n * mh);
         w.bs = take(max_b * mh);
-        w.att = take(M.stats.max_nnz * mh);     // per-entry arrays: one per head
+        w.att = take(M.stats.max_nnz * mh * (c->keep_forward ? (int64_t)L * M.k : 1));   // per-entry arrays: one per head
         w.dal = take(M.stats.max_nnz * mh);
         w.twatt = take(M.stats.max_nnz * mh);
         w.pair = take(M.stats.max_nnz * mh * 2);
@@ -1114,6 +1128,7 @@ gnn_status gnn_build_partitions(gnn_ctx* c, int64_t n, const int64_t* rowptr, co
     c->loss_done = false;
     c->fwd_done.assign((size_t)c->L * (size_t)k, 0);
     c->xf_fwd_done.assign((size_t)c->L * (size_t)k, 0);
+    c->att_done.assign((size_t)c->L * (size_t)k, 0);
     c->xf_bwd_done.assign((size_t)c->L * (size_t)k, 0);
     c->bwd_done.assign((size_t)c->L + 2, 0);
     compute_workspace(c);
@@ -1252,6 +1267,7 @@ gnn_status gnn_bind(gnn_ctx* c, const void* feat, void* const* act, void* const*
     c->loss_done = false;
     std::fill(c->fwd_done.begin(), c->fwd_done.end(), 0);
     std::fill(c->xf_fwd_done.begin(), c->xf_fwd_done.end(), 0);
+    std::fill(c->att_done.begin(), c->att_done.end(), 0);
     std::fill(c->xf_bwd_done.begin(), c->xf_bwd_done.end(), 0);
     std::fill(c->bwd_done.begin(), c->bwd_done.end(), 0);
     c->h_layer = 0;
@@ -1411,6 +1427,20 @@ gnn_status gnn_set_gat_heads(gnn_ctx* c, int32_t layer, int32_t heads)
     return GNN_OK;
 }
 
+gnn_status gnn_set_keep_forward(gnn_ctx* c, int32_t on)
+{
+    if (!c) return GNN_EINVAL;
+    if (on != 0 && on != 1) return c->fail(GNN_EINVAL, "gnn_set_keep_forward takes 0 or 1");
+    if (c->keep_forward == (on == 1)) return GNN_OK;
+    c->keep_forward = on == 1;
+    if (c->model == GNN_GAT && !c->streaming()) {
+        c->bound = false;          // workspace sizes depend on it
+        c->h_layer = 0;
+        if (c->built) compute_workspace(c);
+    }
+    return GNN_OK;
+}
+
 gnn_status gnn_layer_is_transform_first(const gnn_ctx* c, int32_t layer, int32_t* out)
 {
     if (!c || !out) return GNN_EINVAL;
@@ -1427,11 +1457,16 @@ gnn_status gnn_layer_transform_fwd(gnn_ctx* c, int32_t layer, int32_t p, void* s
     if (!c->transform_first(layer)) return c->fail(GNN_ESTATE, "this layer aggregates first");
     hipStream_t s = (hipStream_t)stream;
     const HostMeta& M = c->M;
+    const bool kept = c->model == GNN_GAT && c->keep_forward;
     if (c->h_layer != layer) {
-        // one buffer holds H for whichever layer is being worked on
-        std::fill(c->xf_fwd_done.begin(), c->xf_fwd_done.end(), 0);
+        // one buffer holds H for whichever layer is being worked on (attention that keeps its
+        // forward results: one per layer)
+        if (!kept) std::fill(c->xf_fwd_done.begin(), c->xf_fwd_done.end(), 0);
         c->h_layer = layer;
     }
+    if (c->model == GNN_GAT)      // attention weights taken from the old rows of H are void
+        std::fill(c->att_done.begin() + (size_t)(layer - 1) * (size_t)M.k,
+                  c->att_done.begin() + (size_t)layer * (size_t)M.k, 0);
     if (c->model == GNN_GAT) gat_transform_fwd(c, layer, p, s);
     else xf_transform_fwd(c, layer, p, c->layer_input(layer, M.off[(size_t)p]), s);
     c->xf_fwd_done[(size_t)(layer - 1) * (size_t)M.k + (size_t)p] = 1;
@@ -1729,7 +1764,8 @@ static gnn_status epoch_resident(gnn_ctx* c, void* stream, float* loss_out)
     for (int32_t l = L; l >= 1; --l) {
         const bool xf = c->transform_first(l);
         const bool regather = !xf || c->model == GNN_GAT;
-        if (c->model == GNN_GAT && c->h_layer != l)
+        if (c->model == GNN_GAT && c->h_layer != l &&
+            !(c->keep_forward && all_done(c->xf_fwd_done, l, k) == k))
             // attention needs H and the scores of this layer again: recompute them
             for (int32_t t = 0; t < k; ++t)
                 if ((st = gnn_layer_transform_fwd(c, l, c->M.sched[(size_t)t], stream)) != GNN_OK) return st;

@@ -52,6 +52,9 @@ struct Workspace {  // byte offsets into `scratch`
     int64_t z = 0, dy = 0, dz = 0, dga = 0, partial = 0, colpart = 0, losspart = 0, scalars = 0,
             segpart = 0;
     int64_t h = 0, gh = 0;     // transform-first layers: H = A W and its gradient, n x padded width
+    // graph attention keeping its forward results (gnn_set_keep_forward): floats from `h` to the
+    // H of layer l (at [l - 1]); empty otherwise (one H buffer serves every layer in turn)
+    std::vector<int64_t> gat_h_off;
     int64_t h_floats = 0;      // size of that buffer (0: no layer transforms first); the streaming
     int64_t dyall_floats = 0;  // schedule takes it, and the kept dY rows, out of its HBM budget
     int64_t wpad = 0;          // and copies of W, W_s with rows padded to that width (2 x d_in x padded)
@@ -163,6 +166,10 @@ struct gnn_ctx {
     }
     // width of H rows: d_layer rounded up to whole 16-byte vectors
     int32_t padded(int32_t layer) const { return (dims[(size_t)layer] + 3) / 4 * 4; }
+    // graph attention, resident: H, the scores and the attention weights of every layer stay from
+    // the forward pass until the backward pass has used them (memory instead of recomputation)
+    bool keep_forward = false;
+    std::vector<uint8_t> att_done;       // L * k: attention weights of (layer, partition) are those of this H
     // graph attention: heads of layer l at [l - 1] (empty: one head everywhere).  With several
     // heads H, grad H and the staged rows are kept head by head: head j of a layer is an array
     // of its own with head_padded(l) floats per vertex (its f = d_l / heads columns rounded up to

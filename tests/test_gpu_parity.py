@@ -1320,7 +1320,19 @@ def test_multi_head_attention_epoch_matches_oracle(name, dims, heads, k, mode):
         for a, b in zip(got[key], r3[key]):
             assert np.array_equal(a, b), ("fused gather", key)
     assert bool((s.staging == 0xFF).all()), "staging was written although the gather is fused"
+    # forward results kept for the backward pass (H, scores, attention weights of every layer)
+    # instead of recomputed: more workspace, the same bits, epoch after epoch
+    ws_plain = s.ctx.workspace_bytes()
     del s
+    keep = Session("gat", dims, rowptr, colidx, k, mode, cfg["seed"], X, w, y, m, fuse_gather=True, keep_forward=True)
+    assert keep.ctx.workspace_bytes()[1] > ws_plain[1]
+    for rep in range(2):
+        assert keep.epoch() == loss
+        r4 = keep.results()
+        for key in ("act", "gact", "gW", "gWs", "gb"):
+            for a, b in zip(got[key], r4[key]):
+                assert np.array_equal(a, b), ("kept forward results", rep, key)
+    del keep
     # the heads matter: the one-head model of the same weights gives another loss
     for wl in w:
         wl["heads"] = 1

@@ -259,3 +259,15 @@ def test_errors_of_the_training_order_and_attention_entry_points():
     gat.set_gat_heads(1, 1)
     gat.set_gat_heads(2, 1)
     assert gat.workspace_bytes() == before
+    # keeping the forward results of attention layers: more workspace; nothing for other models
+    before = gat.workspace_bytes()
+    gat.set_keep_forward(True)
+    assert gat.workspace_bytes()[1] > before[1]
+    gat.set_keep_forward(False)
+    assert gat.workspace_bytes() == before
+    before = gcn.workspace_bytes()
+    gcn.set_keep_forward(True)
+    assert gcn.workspace_bytes() == before
+    with pytest.raises(GnnError) as e:
+        gat._check(gat.lib.gnn_set_keep_forward(gat.h, 2))
+    assert e.value.status == 1
