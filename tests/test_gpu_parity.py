@@ -1387,7 +1387,8 @@ def test_attention_dropout_epoch_and_training_steps_match_oracle(dims, heads, dr
     assert abs(loss - ref["loss"]) <= TOL * abs(ref["loss"])
     check(got, ref, "dropout epoch")
     for opt, lr in (("adam", 0.01), ("sgd", 0.05)):
-        s = Session("gat", dims, rowptr, colidx, k, "lp", seed, X, w, y, m)
+        # (the Adam run keeps its forward results for the backward pass, the SGD run recomputes them)
+        s = Session("gat", dims, rowptr, colidx, k, "lp", seed, X, w, y, m, keep_forward=opt == "adam")
         losses = s.train(3, optimizer=opt, lr=lr, weight_decay=0.01, dropout=dropout, seed=7)
         ref_losses, ref_w, _ = ogat.train(rowptr, colidx, dims, X, w, y, m, epochs=3, optimizer=opt, lr=lr,
                                           weight_decay=0.01, dropout=dropout, seed=7)
