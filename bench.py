@@ -40,7 +40,7 @@ def padded_width(d):
 
 
 def algorithmic_bytes(stats, dims, model, n_parts, es=4, fused_scatter=False, xf=None, pad=padded_width,
-                      masked=None, first_touch=False):
+                      masked=None, first_touch=False, kept=False):
     """HBM bytes the method has to move per epoch, by kernel class (lower bound: every needed
     source row is read once per partition).  es = bytes per stored activation (4 fp32, 2 bf16);
     gradients of activations are always fp32.  xf[l-1]: layer l transforms first, so it
@@ -50,7 +50,9 @@ def algorithmic_bytes(stats, dims, model, n_parts, es=4, fused_scatter=False, xf
     that pass then reads only those entries and the gradient rows of train vertices, and adds
     onto `rows` rows.  first_touch: the epoch stores the first contribution to a row of a
     gradient array instead of adding it onto a zeroed one (every row once: n rows are written
-    without being read; not with the operator over train vertices)."""
+    without being read; not with the operator over train vertices).  kept: aggregate-first layers
+    keep their aggregate from the forward pass, so the backward pass neither regathers nor
+    aggregates again."""
     n, nnz, k = stats["n"], stats["nnz"], stats["k"]
     sum_r = n + stats["sum_boundary"]            # sum over partitions of |own_p| + |B_p|
     sum_b = stats["sum_boundary"]
@@ -81,10 +83,10 @@ def algorithmic_bytes(stats, dims, model, n_parts, es=4, fused_scatter=False, xf
         row = d * es
         grow = d * 4
         # forward + backward regather
-        out["gather"] += 2 * (2 * sum_b * row + 4 * sum_b)
+        out["gather"] += (1 if kept else 2) * (2 * sum_b * row + 4 * sum_b)
         # forward + recompute
         spmm = per_entry * nnz + 8 * (n + k) + sum_r * row + n * row + (4 * n if model == "sage" else 0)
-        out["spmm"] += 2 * spmm
+        out["spmm"] += (1 if kept else 2) * spmm
         if l >= 2:
             if fused_scatter and masked and l == L:
                 m_e, m_r, m_v = masked
@@ -226,12 +228,13 @@ def run_workload(name, args, steps, warmup, want_cpu):
     s = Session(model, dims, rowptr, colidx, cfg["k"], cfg["part"], cfg["seed"], X, w, y, m,
                 dtype=cfg["dtype"], hbm_budget_bytes=budget,
                 layer_order=args.layer_order, fuse_gather=not args.staged_gather,
-                keep_forward=(model == "gat" and not args.gat_recompute),
+                keep_forward=(False if args.recompute or budget else "auto"),
                 masked_backward=not args.full_backward, storage_dir=args.storage_dir,
                 host_budget_bytes=int(args.host_budget_gb * 2 ** 30), progress=lambda msg: log("  " + msg))
     if args.storage_dir and args.storage_drop_results:
         s.ctx.storage_keep_results(False)
     gather_fused = s.ctx.gather_is_fused()
+    keeps_forward = s.keeps_forward        # (as the timed epochs run; the paper-order run below recomputes)
     m_entries, m_rows = s.ctx.masked_backward_size()
     masked = (m_entries, m_rows, int((m != 0).sum())) if m_rows or m_entries else None
     xf = [s.ctx.layer_is_transform_first(l) for l in range(1, len(dims))]
@@ -312,6 +315,7 @@ def run_workload(name, args, steps, warmup, want_cpu):
     paper_ms, paper_gather = None, None
     if ((args.layer_order == "auto" and any(xf)) or gather_fused) and not args.no_paper_order and \
             model != "gat" and not args.train and not budget:
+        s.set_keep_forward(False)               # the paper's backward pass regathers and recomputes
         if any(xf):
             s.set_layer_order("aggregate")
         s.set_gather_fusion(False)
@@ -338,6 +342,7 @@ def run_workload(name, args, steps, warmup, want_cpu):
                                 "algorithmic_GBps": g_bytes / (g_ms * 1e-3) / 1e9,
                                 "frac_hbm_peak": g_bytes / (g_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
     elif args.layer_order == "auto" and any(xf) and not args.no_paper_order and model != "gat" and not args.train:
+        s.set_keep_forward(False)
         s.set_layer_order("aggregate")
         for i in range(min(warmup, 1)):
             s.epoch()
@@ -369,9 +374,9 @@ def run_workload(name, args, steps, warmup, want_cpu):
                    "dims": list(dims), "k": stats["k"], "partitioner": cfg["part"],
                    "alpha": stats["sum_required"] / n, "sum_boundary": stats["sum_boundary"],
                    "layer_order": ["transform-first" if t else "aggregate-first" for t in xf],
-                   **({"attention_forward_results": "recomputed in the backward pass" if args.gat_recompute
-                       else "kept for the backward pass (H, scores, attention weights of every layer)"}
-                      if model == "gat" else {}),
+                   "forward_results": ("kept for the backward pass (aggregate of aggregate-first layers; H, scores "
+                                       "and attention weights of attention layers)" if keeps_forward
+                                       else "recomputed in the backward pass (regather + recompute)"),
                    "gather": ("fused into the aggregation (rows read from the whole-graph array through B_p)"
                               if gather_fused else "a step of its own, through the staging buffer"),
                    "output_layer_backward": ("%d operator entries of train vertices of %d (the loss gradient is "
@@ -391,7 +396,7 @@ def run_workload(name, args, steps, warmup, want_cpu):
         out["config"]["gradient_rows_first_touch_store"] = first_touch
         ab = algorithmic_bytes(stats, dims, model, stats["k"], es,
                                fused_scatter=prof.get("scatter", (0, 0))[1] == 0, xf=xf, masked=masked,
-                               first_touch=first_touch)
+                               first_touch=first_touch, kept=keeps_forward)
         if gather_fused:
             ab["gather"] = 0                    # no staging copy is made
         fused = fused_layers(dims, xf, cfg["dtype"]) if model != "gat" else []
@@ -511,9 +516,10 @@ def main():
     ap.add_argument("--graph-scale", type=float, default=1.0,
                     help="shrink the workload's graph (vertices and drawn edges) by this factor; "
                          "for runs that would not fit the host otherwise")
-    ap.add_argument("--gat-recompute", action="store_true",
-                    help="graph-attention workloads: recompute H, the scores and the attention weights in the "
-                         "backward pass (the paper's rule) instead of keeping them from the forward pass")
+    ap.add_argument("--recompute", action="store_true",
+                    help="recompute in the backward pass what the forward pass computed (the paper's rule: the "
+                         "aggregate of aggregate-first layers; H, scores and attention weights of attention "
+                         "layers) instead of keeping it in device memory when it fits")
     ap.add_argument("--gat-heads", default=None,
                     help="graph-attention workloads: attention heads per layer, comma-separated (e.g. 8,8,1)")
     ap.add_argument("--train", action="store_true",

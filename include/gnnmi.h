@@ -374,19 +374,25 @@ gnn_status gnn_layer_transform_bwd(gnn_ctx *ctx, int32_t layer, int32_t p, void 
  * 1..L, or a head count outside 1..64 or not dividing d_l. */
 gnn_status gnn_set_gat_heads(gnn_ctx *ctx, int32_t layer, int32_t heads);
 
-/* GNN_GAT, resident schedule: keep what the forward pass computed for the backward pass. The
- * paper's backward pass regathers and recomputes because device memory is what it is short of;
- * with on = 1 the context keeps H = A^{l-1} W and the scores of every layer (n rows of the
- * layer's width each, instead of one buffer serving every layer in turn) and the attention
- * weights of every layer and partition (4 bytes per operator entry, head and layer), all inside
- * `scratch`, so that gnn_epoch does not run gnn_layer_transform_fwd again before a layer's
- * backward sweep and gnn_layer_bwd does not recompute the attention weights.  Kept values are
- * the values the recomputation would give: every result has the same bits.  Stepping by hand:
- * H "still holds this layer" for every layer whose gnn_layer_transform_fwd has covered every
- * partition, and a partition's attention weights are kept from its gnn_layer_fwd until the next
- * gnn_layer_transform_fwd of that layer.  Default 0.  Changes the workspace sizes: call before
- * gnn_workspace_bytes / gnn_bind (a bound GNN_GAT context becomes unbound).  No effect on other
- * models.  GNN_EINVAL for on outside {0, 1}. */
+/* Resident schedule: keep what the forward pass computed for the backward pass.  The paper's
+ * backward pass regathers and recomputes (gradient engine: activation regathering, snapshot
+ * avoided) because device memory is what its hierarchy is short of; with on = 1 the context keeps,
+ * inside `scratch`,
+ *   GNN_GCN, GNN_SAGE_MEAN: the aggregate Z = S A^{l-1} of every layer that aggregates first (n
+ *     rows of d_{l-1} elements of the storage type per such layer); gnn_layer_bwd of such a layer
+ *     then needs no gnn_gather_boundary before it and aggregates nothing again (gnn_epoch
+ *     regathers nothing there);
+ *   GNN_GAT: H = A^{l-1} W and the scores of every layer (n rows of the layer's width each,
+ *     instead of one buffer serving every layer in turn) and the attention weights of every layer
+ *     and partition (4 bytes per operator entry, head and layer), so that gnn_epoch does not run
+ *     gnn_layer_transform_fwd again before a layer's backward sweep and gnn_layer_bwd does not
+ *     recompute the attention weights.
+ * Kept values are the values the recomputation would give: every result has the same bits.  A
+ * partition's kept values are those of its latest gnn_layer_fwd (attention: until the next
+ * gnn_layer_transform_fwd of that layer); a backward pass that finds none recomputes as without
+ * the switch.  Default 0 (the paper's rule).  Changes the workspace sizes: call before
+ * gnn_workspace_bytes / gnn_bind (a bound context becomes unbound).  No effect with a streaming
+ * budget.  GNN_EINVAL for on outside {0, 1}. */
 gnn_status gnn_set_keep_forward(gnn_ctx *ctx, int32_t on);
 
 /* ---- training around the epoch (datasets table: learning rate, dropout, epochs) ---------- */

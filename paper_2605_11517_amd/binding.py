@@ -395,7 +395,9 @@ class Session:
         self.ctx.set_layer_order(layer_order)
         self.ctx.set_gather_fusion(fuse_gather)
         self.ctx.set_masked_backward(masked_backward)
-        self.ctx.set_keep_forward(keep_forward)
+        # keep_forward: True / False, or "auto": kept when the larger workspace fits the device
+        # memory that is free once everything else is allocated (decided below)
+        self.ctx.set_keep_forward(keep_forward is True)
         if _MODEL.get(model, model) == GNN_GAT:
             # attention heads per layer: weights[l]["heads"] (default 1)
             for l, wl in enumerate(weights):
@@ -466,13 +468,42 @@ class Session:
                     self.w.append(None)
                     self.gw.append(None)
                     self.w32.append(None)
-        sb, wb = self.ctx.workspace_bytes()
-        self.staging = t.empty(sb, dtype=t.uint8, device=self.dev)
-        self.scratch = t.empty(wb, dtype=t.uint8, device=self.dev)
+        self.keeps_forward = keep_forward is True
+        if keep_forward == "auto" and not self.streaming:
+            self.ctx.set_keep_forward(True)
+            sb, wb = self.ctx.workspace_bytes()
+            free, _ = t.cuda.mem_get_info(self.dev)
+            # (bind still allocates index arrays of its own: the second copy of the column
+            # indices, 4 bytes per operator entry, and the output layer's operator over train
+            # vertices, a fraction of that)
+            margin = 4 * 2 ** 30 + 6 * int(rowptr[-1])
+            self.keeps_forward = sb + wb + margin <= free
+            if not self.keeps_forward:
+                self.ctx.set_keep_forward(False)
+            say("forward results %s (workspace %.1f GiB, %.1f GiB free)"
+                % ("kept" if self.keeps_forward else "recomputed", (sb + wb) / 2 ** 30, free / 2 ** 30))
         ptr = lambda x: x.data_ptr() if x is not None else None
-        self.ctx.bind(ptr(self.feat), [ptr(a) for a in self.act], [ptr(g) for g in self.gact],
-                      [ptr(w) for w in self.w], [ptr(g) for g in self.gw], ptr(self.labels),
-                      ptr(self.mask), ptr(self.staging), ptr(self.scratch))
+
+        def allocate_and_bind():
+            sb, wb = self.ctx.workspace_bytes()
+            self.staging = t.empty(sb, dtype=t.uint8, device=self.dev)
+            self.scratch = t.empty(wb, dtype=t.uint8, device=self.dev)
+            self.ctx.bind(ptr(self.feat), [ptr(a) for a in self.act], [ptr(g) for g in self.gact],
+                          [ptr(w) for w in self.w], [ptr(g) for g in self.gw], ptr(self.labels),
+                          ptr(self.mask), ptr(self.staging), ptr(self.scratch))
+
+        try:
+            allocate_and_bind()
+        except (GnnError, RuntimeError):
+            # "auto" misjudged the room: bind again with the smaller workspace
+            if not (keep_forward == "auto" and self.keeps_forward):
+                raise
+            say("not enough device memory with kept forward results: recomputing instead")
+            self.staging = self.scratch = None
+            t.cuda.empty_cache()
+            self.ctx.set_keep_forward(False)
+            self.keeps_forward = False
+            allocate_and_bind()
         say("bound")
         t.cuda.synchronize()
         del stream
@@ -515,6 +546,27 @@ class Session:
         t = self.torch
         t.cuda.synchronize()
         self.ctx.set_layer_order(mode)
+        self.staging = self.scratch = None
+        t.cuda.empty_cache()
+        sb, wb = self.ctx.workspace_bytes()
+        self.staging = t.empty(sb, dtype=t.uint8, device=self.dev)
+        self.scratch = t.empty(wb, dtype=t.uint8, device=self.dev)
+        ptr = lambda x: x.data_ptr() if x is not None else None
+        self.ctx.bind(ptr(self.feat), [ptr(a) for a in self.act], [ptr(g) for g in self.gact],
+                      [ptr(w) for w in self.w], [ptr(g) for g in self.gw], ptr(self.labels),
+                      ptr(self.mask), ptr(self.staging), ptr(self.scratch))
+        t.cuda.synchronize()
+
+    def set_keep_forward(self, on):
+        """Forward results kept for the backward pass (True) or recomputed there (False): the
+        workspace sizes depend on it, so staging and scratch are allocated anew and everything
+        is bound again."""
+        if bool(on) == self.keeps_forward:
+            return
+        t = self.torch
+        t.cuda.synchronize()
+        self.ctx.set_keep_forward(on)
+        self.keeps_forward = bool(on)
         self.staging = self.scratch = None
         t.cuda.empty_cache()
         sb, wb = self.ctx.workspace_bytes()

@@ -285,6 +285,11 @@ void compute_workspace(gnn_ctx* c)
     auto take = [&](int64_t floats) { int64_t at = o; o += align_up(std::max<int64_t>(1, floats) * 4); return at; };
     w.z = take(max_np * din);
     w.z2 = take(max_np * din);
+    w.zkeep.assign((size_t)L, -1);
+    if (c->keep_forward && c->model != GNN_GAT && !c->streaming())
+        for (int32_t l = 1; l <= L; ++l)
+            if (!c->transform_first(l))      // n rows of the layer's input width, storage type
+                w.zkeep[(size_t)l - 1] = take((M.n * (int64_t)c->dims[(size_t)l - 1] * c->es() + 3) / 4);
     w.dy = take(max_np * dout);
     w.dz = take(max_np * din);
     w.dga = take(max_r * din);
@@ -379,7 +384,7 @@ void run_spmm_fwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, hipS
     SpmmItems items = plan_items(M.plan_fwd, c->D.fwd, p);
     items.avg_len = (float)(M.rp[(size_t)M.off[(size_t)p + 1]] - M.rp[(size_t)r0]) / (float)std::max<int64_t>(1, np);
     const float* rscale = c->D.rscale ? c->D.rscale + r0 : nullptr;
-    void* Z = c->scratch + c->z_off();
+    void* Z = c->z_region(layer, p);
     float* segpart = (float*)(c->scratch + c->ws.segpart);
     const int b16 = c->bf16() ? 1 : 0;
     {
@@ -510,6 +515,7 @@ void compute_fwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, char*
         }
     }
     run_spmm_fwd(c, layer, p, in_own, s);
+    if (c->keeps_z(layer)) c->z_done[(size_t)(layer - 1) * (size_t)c->M.k + (size_t)p] = 1;
     if (c->fwd_side) {
         // gnn_epoch, resident: the contraction (and the dropout behind it) goes to the side stream
         // once Z is complete, and the caller's stream moves on to the next partition's gather
@@ -541,7 +547,7 @@ void compute_fwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, char*
     const bool sage = c->model == GNN_SAGE_MEAN;
     if (!c->bf16()) {
         GemmSeg seg[2];
-        seg[0].a = (const float*)(c->scratch + c->z_off()); seg[0].lda = din;
+        seg[0].a = (const float*)c->z_region(layer, p); seg[0].lda = din;
         seg[0].b = (const float*)c->w[(size_t)3 * (layer - 1)]; seg[0].ldb = dout; seg[0].k = din;
         if (sage) {
             seg[1].a = (const float*)in_own; seg[1].lda = din;
@@ -550,7 +556,7 @@ void compute_fwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own, char*
         launch_gemm_nn(seg, sage ? 2 : 1, (float*)out_own, dout, np, dout, ep, s);
     } else {
         GemmSegBf16 seg[2];
-        seg[0].a = c->scratch + c->z_off(); seg[0].lda = din;
+        seg[0].a = c->z_region(layer, p); seg[0].lda = din;
         seg[0].b = c->w[(size_t)3 * (layer - 1)]; seg[0].ldb = dout; seg[0].k = din;
         if (sage) {
             seg[1].a = in_own; seg[1].lda = din;
@@ -624,7 +630,7 @@ const char* compute_bwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own
     float* gW = c->gw[(size_t)3 * (layer - 1)];
     float* gWs = c->gw[(size_t)3 * (layer - 1) + 1];
     float* gb = c->has_bias ? c->gw[(size_t)3 * (layer - 1) + 2] : nullptr;
-    char* Z = c->scratch + c->ws.z;
+    char* Z = c->z_region(layer, p);
     char* dYbuf = c->scratch + c->ws.dy;
     char* dZ = c->scratch + c->ws.dz;
     float* dGA = (float*)(c->scratch + c->ws.dga);
@@ -651,8 +657,9 @@ const char* compute_bwd(gnn_ctx* c, int32_t layer, int32_t p, const char* in_own
                            c->streaming() ? nullptr : c->mask + M.off[(size_t)p]);
         }
     }
-    // recompute the aggregate from the regathered rows
-    run_spmm_fwd(c, layer, p, in_own, s);
+    // recompute the aggregate from the regathered rows (unless the forward pass's is kept)
+    if (!(c->keeps_z(layer) && c->z_done[(size_t)(layer - 1) * (size_t)M.k + (size_t)p]))
+        run_spmm_fwd(c, layer, p, in_own, s);
     // weight gradients, summed over partitions
     {
         Timed t(c, s, GNN_K_GEMM_DW);
@@ -1129,6 +1136,7 @@ gnn_status gnn_build_partitions(gnn_ctx* c, int64_t n, const int64_t* rowptr, co
     c->fwd_done.assign((size_t)c->L * (size_t)k, 0);
     c->xf_fwd_done.assign((size_t)c->L * (size_t)k, 0);
     c->att_done.assign((size_t)c->L * (size_t)k, 0);
+    c->z_done.assign((size_t)c->L * (size_t)k, 0);
     c->xf_bwd_done.assign((size_t)c->L * (size_t)k, 0);
     c->bwd_done.assign((size_t)c->L + 2, 0);
     compute_workspace(c);
@@ -1268,6 +1276,7 @@ gnn_status gnn_bind(gnn_ctx* c, const void* feat, void* const* act, void* const*
     std::fill(c->fwd_done.begin(), c->fwd_done.end(), 0);
     std::fill(c->xf_fwd_done.begin(), c->xf_fwd_done.end(), 0);
     std::fill(c->att_done.begin(), c->att_done.end(), 0);
+    std::fill(c->z_done.begin(), c->z_done.end(), 0);
     std::fill(c->xf_bwd_done.begin(), c->xf_bwd_done.end(), 0);
     std::fill(c->bwd_done.begin(), c->bwd_done.end(), 0);
     c->h_layer = 0;
@@ -1433,7 +1442,7 @@ gnn_status gnn_set_keep_forward(gnn_ctx* c, int32_t on)
     if (on != 0 && on != 1) return c->fail(GNN_EINVAL, "gnn_set_keep_forward takes 0 or 1");
     if (c->keep_forward == (on == 1)) return GNN_OK;
     c->keep_forward = on == 1;
-    if (c->model == GNN_GAT && !c->streaming()) {
+    if (!c->streaming()) {
         c->bound = false;          // workspace sizes depend on it
         c->h_layer = 0;
         if (c->built) compute_workspace(c);
@@ -1593,7 +1602,9 @@ gnn_status gnn_layer_bwd(gnn_ctx* c, int32_t layer, int32_t p, void* stream)
         c->bwd_done[(size_t)layer] += 1;
         return check_launch(c, "gnn_layer_bwd");
     }
-    if (c->staged_layer != layer || c->staged_p != p)
+    // (a kept aggregate needs no regathered rows)
+    const bool kept_z = c->keeps_z(layer) && c->z_done[(size_t)(layer - 1) * (size_t)c->M.k + (size_t)p];
+    if (!kept_z && (c->staged_layer != layer || c->staged_p != p))
         return c->fail(GNN_ESTATE, "staging does not hold this (layer, partition); call gnn_gather_boundary first");
     const HostMeta& M = c->M;
     const int64_t r0 = M.off[(size_t)p], np = M.off[(size_t)p + 1] - r0;
@@ -1774,7 +1785,8 @@ static gnn_status epoch_resident(gnn_ctx* c, void* stream, float* loss_out)
             if (wait_steps &&
                 (st = hip_ok(hipStreamWaitEvent(s, step_event[t], 0), "hipStreamWaitEvent")) != GNN_OK)
                 return st;
-            if (regather && (st = gnn_gather_boundary(c, l, p, stream)) != GNN_OK) return st;
+            const bool kept = c->keeps_z(l) && c->z_done[(size_t)(l - 1) * (size_t)k + (size_t)p];
+            if (regather && !kept && (st = gnn_gather_boundary(c, l, p, stream)) != GNN_OK) return st;
             if ((st = gnn_layer_bwd(c, l, p, stream)) != GNN_OK) return st;
         }
         wait_steps = false;

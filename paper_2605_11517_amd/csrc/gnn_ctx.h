@@ -55,6 +55,9 @@ struct Workspace {  // byte offsets into `scratch`
     // graph attention keeping its forward results (gnn_set_keep_forward): floats from `h` to the
     // H of layer l (at [l - 1]); empty otherwise (one H buffer serves every layer in turn)
     std::vector<int64_t> gat_h_off;
+    // aggregate-first layers keeping their aggregate Z = S A^{l-1} (gnn_set_keep_forward): byte
+    // offset of layer l's whole-graph array (n x d_{l-1}, storage type) at [l - 1], -1: not kept
+    std::vector<int64_t> zkeep;
     int64_t h_floats = 0;      // size of that buffer (0: no layer transforms first); the streaming
     int64_t dyall_floats = 0;  // schedule takes it, and the kept dY rows, out of its HBM budget
     int64_t wpad = 0;          // and copies of W, W_s with rows padded to that width (2 x d_in x padded)
@@ -170,6 +173,20 @@ struct gnn_ctx {
     // the forward pass until the backward pass has used them (memory instead of recomputation)
     bool keep_forward = false;
     std::vector<uint8_t> att_done;       // L * k: attention weights of (layer, partition) are those of this H
+    std::vector<uint8_t> z_done;         // L * k: the kept aggregate of (layer, partition) is that of this forward pass
+    // where the aggregate of (layer, partition) goes: its rows of the kept whole-graph array, or
+    // the per-partition scratch region
+    bool keeps_z(int32_t layer) const
+    {
+        return keep_forward && !streaming() && model != GNN_GAT && (size_t)layer <= ws.zkeep.size() &&
+               ws.zkeep[(size_t)layer - 1] >= 0;
+    }
+    char* z_region(int32_t layer, int32_t p) const
+    {
+        if (keeps_z(layer))
+            return scratch + ws.zkeep[(size_t)layer - 1] + M.off[(size_t)p] * (int64_t)dims[(size_t)layer - 1] * es();
+        return scratch + z_off();
+    }
     // graph attention: heads of layer l at [l - 1] (empty: one head everywhere).  With several
     // heads H, grad H and the staged rows are kept head by head: head j of a layer is an array
     // of its own with head_padded(l) floats per vertex (its f = d_l / heads columns rounded up to

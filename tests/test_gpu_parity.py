@@ -1196,6 +1196,75 @@ def test_side_stream_overlap_gives_the_one_stream_bits(monkeypatch, name, dims, 
                 assert np.array_equal(la[key], lb[key]), key
 
 
+@pytest.mark.parametrize("model,dims,order,dtype,fuse", [
+    ("sage", (100, 256, 256, 47), "auto", "f32", True),        # layer 1 keeps its aggregate
+    ("sage", (24, 40, 40, 7), "aggregate", "f32", False),      # every layer does, through staging
+    ("gcn", (64, 64, 16), "aggregate", "f32", True),
+    ("gcn", (72, 136, 8), "aggregate", "bf16", False),
+])
+def test_kept_aggregates_give_the_bits_of_the_recomputed_ones(model, dims, order, dtype, fuse):
+    """gnn_set_keep_forward(1): aggregate-first layers keep Z = S A^{l-1} from the forward pass and
+    the backward pass neither regathers nor aggregates again.  The kept rows are the rows the
+    recomputation would give: every result has the same bits, epoch after epoch, with dropout, and
+    stepping by hand the backward pass needs no gather."""
+    say("case kept aggregates %s %s %s %s fused=%s" % (model, dims, order, dtype, fuse))
+    import torch
+    from paper_2605_11517_amd import Session
+    n, k, seed = 3000, 5, 21
+    rowptr, colidx = small_graph(n, 40000, seed=4, symmetric=True, self_loops=model == "gcn")
+    cfg = dict(model=model, dims=dims, seed=seed, train_frac=0.5)
+    X, y, m, w = make_inputs(cfg, n)
+    L = len(dims) - 1
+    keys = ("act", "gact", "gW", "gWs", "gb")
+    res = {}
+    for keep in (False, True, "auto"):
+        s = Session(model, dims, rowptr, colidx, k, "lp", seed, X, w, y, m, dtype=dtype, layer_order=order,
+                    fuse_gather=fuse, keep_forward=keep)
+        assert s.keeps_forward == (keep is not False)
+        s.ctx.set_dropout(0.3, 5, 1)
+        out = []
+        for rep in range(2):
+            loss = s.epoch()
+            out.append((loss, s.results()))
+        res[keep] = (out, s.ctx.workspace_bytes()[1])
+        if keep is True:
+            # by hand: forward, loss, then the backward pass without any gather
+            st = s.stream
+            xf = [s.ctx.layer_is_transform_first(l) for l in range(1, L + 1)]
+            for g in s.gw:
+                if g is not None:
+                    g.zero_()
+            torch.cuda.synchronize()
+            for l in range(1, L + 1):
+                if xf[l - 1]:
+                    for p in range(k):
+                        s.ctx.layer_transform_fwd(l, p, st)
+                for p in range(k):
+                    s.ctx.gather_boundary(l, p, st)
+                    s.ctx.layer_fwd(l, p, st)
+            s.ctx.loss(st)
+            for l in range(L, 0, -1):
+                for p in range(k):
+                    s.ctx.layer_bwd(l, p, st)          # no gnn_gather_boundary: nothing is regathered
+                if xf[l - 1]:
+                    for p in range(k):
+                        s.ctx.layer_transform_bwd(l, p, st)
+            hand = s.results()
+            for key in keys:
+                for a, b in zip(out[-1][1][key], hand[key]):
+                    if a is not None:
+                        assert np.array_equal(a, b), ("by hand", key)
+        del s
+    assert res[True][1] > res[False][1] and res["auto"][1] == res[True][1]
+    for keep in (True, "auto"):
+        for rep in range(2):
+            assert res[keep][0][rep][0] == res[False][0][rep][0]
+            for key in keys:
+                for a, b in zip(res[False][0][rep][1][key], res[keep][0][rep][1][key]):
+                    if a is not None:
+                        assert np.array_equal(a, b), (keep, rep, key)
+
+
 # ----------------------------------------------------------------------------------------
 # graph attention
 # ----------------------------------------------------------------------------------------

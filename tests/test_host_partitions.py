@@ -259,7 +259,9 @@ def test_errors_of_the_training_order_and_attention_entry_points():
     gat.set_gat_heads(1, 1)
     gat.set_gat_heads(2, 1)
     assert gat.workspace_bytes() == before
-    # keeping the forward results of attention layers: more workspace; nothing for other models
+    # keeping forward results for the backward pass: more workspace (attention: H, scores and
+    # attention weights per layer; the others: the aggregate of aggregate-first layers, n rows of
+    # the input width per layer)
     before = gat.workspace_bytes()
     gat.set_keep_forward(True)
     assert gat.workspace_bytes()[1] > before[1]
@@ -267,6 +269,8 @@ def test_errors_of_the_training_order_and_attention_entry_points():
     assert gat.workspace_bytes() == before
     before = gcn.workspace_bytes()
     gcn.set_keep_forward(True)
+    assert gcn.workspace_bytes()[1] >= before[1] + 30 * (8 + 8) * 4      # dims (8, 8, 4): two layers keep 8 floats per vertex
+    gcn.set_keep_forward(False)
     assert gcn.workspace_bytes() == before
     with pytest.raises(GnnError) as e:
         gat._check(gat.lib.gnn_set_keep_forward(gat.h, 2))
