@@ -313,6 +313,21 @@ def run_workload(name, args, steps, warmup, want_cpu):
     # and recompute in the backward pass of every layer): context, not the headline
     # and with the gather as a step of its own, through the staging buffer
     paper_ms, paper_gather = None, None
+    # the timed schedule with the paper's backward rule: forward results recomputed (regather +
+    # recompute of aggregate-first layers; H, scores and attention weights of attention layers)
+    recompute_ms = None
+    if keeps_forward and not args.no_paper_order and not args.train and not budget:
+        s.set_keep_forward(False)
+        for i in range(min(warmup, 1)):
+            s.epoch()
+        torch.cuda.synchronize()
+        t3 = time.perf_counter()
+        reps = max(1, min(steps, 3))
+        for i in range(reps):
+            s.epoch()
+        torch.cuda.synchronize()
+        recompute_ms = (time.perf_counter() - t3) / reps * 1e3
+        log("[%s] forward results recomputed in the backward pass: epoch %.2f ms" % (name, recompute_ms))
     if ((args.layer_order == "auto" and any(xf)) or gather_fused) and not args.no_paper_order and \
             model != "gat" and not args.train and not budget:
         s.set_keep_forward(False)               # the paper's backward pass regathers and recomputes
@@ -386,6 +401,9 @@ def run_workload(name, args, steps, warmup, want_cpu):
                    "setup_s": setup_s},
         "loss": loss,
     }
+    if recompute_ms is not None:
+        # the same schedule with the paper's backward rule (nothing kept from the forward pass)
+        out["ms_per_step_recompute"] = recompute_ms
     if paper_ms is not None:
         out["ms_per_step_paper_order"] = paper_ms
         if paper_gather is not None:
