@@ -222,9 +222,7 @@ def gat_sampled_errors(rowptr, colidx, dims, weights, X, act, gact, gb, V, say=N
     n = len(rowptr) - 1
     L = len(dims) - 1
     deg = np.diff(rowptr)
-    dst = np.concatenate([np.repeat(np.arange(n, dtype=np.int64), deg), np.arange(n, dtype=np.int64)])
-    src = np.concatenate([np.asarray(colidx, dtype=np.int64), np.arange(n, dtype=np.int64)])
-    assert not np.any(dst[:rowptr[-1]] == src[:rowptr[-1]])
+    assert not np.any(np.repeat(np.arange(n, dtype=np.int64), deg) == np.asarray(colidx))     # no self-loops stored
     assert np.array_equal(np.bincount(colidx, minlength=n), deg)        # mirrored edges
     A = [X] + list(act)
 
@@ -264,21 +262,29 @@ def gat_sampled_errors(rowptr, colidx, dims, weights, X, act, gact, gb, V, say=N
             ref.append(np.maximum(z, 0.0) if l < L else z)
         worst["act[%d] rows" % (l - 1)] = rel_err(np.asarray(A[l])[V], np.array(ref))
 
-        # per-vertex softmax statistics over all edges, then the input gradient of sampled rows
-        # (the entries are the CSR's, row by row, followed by one self-loop per vertex in vertex
-        # order: per-row maxima and sums are segment reductions plus the self-loop's term)
-        mx = np.full((n, nh), -np.inf)
-        den = np.zeros((n, nh))
-        nnz = int(rowptr[-1])
-        has = deg > 0
-        starts = np.asarray(rowptr[:-1])[has]
+        # Softmax statistics (row maximum and denominator) of the vertices the gradient rows
+        # below ask for: the sampled vertices and their neighbours.  Their entries are their CSR
+        # rows plus one self-loop each; per-row maxima and sums are segment reductions over the
+        # gathered rows plus the self-loop's term.
+        need = np.unique(np.concatenate([around(v) for v in V]))
+        pos = np.full(n, -1, dtype=np.int64)
+        pos[need] = np.arange(len(need))
+        cnt = deg[need].astype(np.int64)
+        first = np.cumsum(cnt) - cnt
+        rows_of = np.repeat(np.arange(len(need)), cnt)
+        ent = np.repeat(np.asarray(rowptr[:-1], dtype=np.int64)[need] - first, cnt) + np.arange(int(cnt.sum()))
+        src_e = np.asarray(colidx, dtype=np.int64)[ent]
+        has = cnt > 0
+        mx = np.full((len(need), nh), -np.inf)
+        den = np.zeros((len(need), nh))
         for j in range(nh):
-            e = leaky(s_src[src, j] + s_dst[dst, j])
-            m1 = e[nnz:].copy()
-            m1[has] = np.maximum(m1[has], np.maximum.reduceat(e[:nnz], starts))
-            ex = np.exp(e - m1[dst])
-            d1 = ex[nnz:].copy()
-            d1[has] += np.add.reduceat(ex[:nnz], starts)
+            e = leaky(s_src[src_e, j] + s_dst[need[rows_of], j])
+            m1 = leaky(s_src[need, j] + s_dst[need, j])              # the self-loops
+            own = m1.copy()
+            m1[has] = np.maximum(m1[has], np.maximum.reduceat(e, first[has]))
+            ex = np.exp(e - m1[rows_of])
+            d1 = np.exp(own - m1)
+            d1[has] += np.add.reduceat(ex, first[has])
             mx[:, j], den[:, j] = m1, d1
             del e, ex
         dY = np.asarray(gact[l - 1], dtype=np.float64)
@@ -297,12 +303,12 @@ def gat_sampled_errors(rowptr, colidx, dims, weights, X, act, gact, gb, V, say=N
             for j, cj in enumerate(cols):
                 # edges u -> t
                 x = s_src[u, j] + s_dst[t, j]
-                alpha = np.exp(leaky(x) - mx[t, j]) / den[t, j]
+                alpha = np.exp(leaky(x) - mx[pos[t], j]) / den[pos[t], j]
                 dx = alpha * (dY[t][:, cj] @ H[u, cj] - c[t, j]) * np.where(x > 0, 1.0, 0.2)
                 dHj = alpha @ dY[t][:, cj] + dx.sum() * a_s[cj]
                 # edges t -> u
                 x = s_src[t, j] + s_dst[u, j]
-                alpha = np.exp(leaky(x) - mx[u, j]) / den[u, j]
+                alpha = np.exp(leaky(x) - mx[pos[u], j]) / den[pos[u], j]
                 dx = alpha * (H[t][:, cj] @ dY[u, cj] - c[u, j]) * np.where(x > 0, 1.0, 0.2)
                 dH[cj] = dHj + dx.sum() * a_d[cj]
             ref.append(dH @ W.T)
