@@ -13,8 +13,8 @@ epoch in reasonable time; there sampled rows and columns of every tensor are rec
 their definitions, each from the path's own inputs to that step, which the oracle's
 aggregation routine and plain numpy can do one by one.
 
-`mid_gat` (graph attention on the `mid` graph): sampled vertices, eight hubs among them, of
-every layer's output and input gradient, by a helper that a CPU test pins to the oracle's
+`mid_gat` (graph attention on the `mid` graph, with one head and with eight): sampled vertices
+(with one head eight hubs among them) of every layer's output and input gradient, by a helper that a CPU test pins to the oracle's
 whole-graph epoch.
 
 `large` (50 M vertices, 870 M entries, k = 64): the same kind of sampled check with the tensors
@@ -422,8 +422,11 @@ def test_mid_gat_workload_sampled(capsys, heads):
     say("GPU epoch done, loss %.6f" % loss)
     deg = np.diff(rowptr)
     rng = np.random.default_rng(5)
-    # (with heads the per-vertex recomputation runs head by head: fewer sampled vertices)
-    V = np.unique(np.concatenate([rng.choice(n, 504 if heads is None else 120, replace=False), np.argsort(deg)[-8:]]))
+    # (with heads the per-vertex recomputation runs head by head: fewer sampled vertices, and the
+    # eight hubs - 10^5 neighbours each - stay with the one-head run; hub rows with several heads
+    # are compared with the whole oracle epoch on the smaller cases)
+    V = (np.unique(np.concatenate([rng.choice(n, 504, replace=False), np.argsort(deg)[-8:]])) if heads is None
+         else np.unique(rng.choice(n, 128, replace=False)))
     lref, gref = og.loss(got["act"][L - 1], y, m)
     assert abs(loss - lref) <= TOL * abs(lref)
     worst = {"gact[%d]" % (L - 1): rel_err(got["gact"][L - 1], gref)}
